@@ -1,0 +1,281 @@
+"""Synthetic workloads for one FDG module worker: the module shapes and the seeded tensors.
+
+This module holds NO arithmetic of the method.  It only says which layers a module has (plain
+data), which shapes its tensors take, and how the synthetic inputs are drawn.  Both the CPU oracle's
+tests and the GPU path's tests / benchmark take their inputs from here, so that the two sides see
+bit-identical inputs while sharing no implementation code.
+
+The shapes stand in for the paper's CIFAR-10 experiments (Section V-A: 32x32 colour images, 10
+classes, batch 128; ResNet / WRN architectures named in Table III).  The dataset itself is not used:
+images are N(0,1) noise, labels are uniform, the gradient arriving from the module above is
+N(0, 1e-2) noise (variance 1e-2, i.e. sigma = 0.1).
+
+Random numbers come from numpy's Philox counter-based generator keyed by (seed, stream id), so any
+tensor can be regenerated on its own, in any order.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+# layer kinds (values are the C ABI's fdg_layer_kind)
+STEM = 0
+BASIC_POSTACT = 1
+BASIC_PREACT = 2
+HEAD_POSTACT = 3
+HEAD_PREACT = 4
+
+KIND_NAMES = {STEM: "stem", BASIC_POSTACT: "basic_postact", BASIC_PREACT: "basic_preact",
+              HEAD_POSTACT: "head_postact", HEAD_PREACT: "head_preact"}
+
+
+@dataclass(frozen=True)
+class Layer:
+    kind: int
+    c_in: int
+    c_out: int = 0
+    stride: int = 1
+
+    @property
+    def is_head(self) -> bool:
+        return self.kind in (HEAD_POSTACT, HEAD_PREACT)
+
+    @property
+    def projects(self) -> bool:
+        return self.kind in (BASIC_POSTACT, BASIC_PREACT) and (self.stride != 1 or self.c_in != self.c_out)
+
+
+@dataclass
+class ModuleSpec:
+    """Plain description of one module; mirrors the C ABI's fdg_module_desc field by field."""
+    n: int
+    c_in: int
+    h_in: int
+    w_in: int
+    layers: List[Layer]
+    delay: int = 0
+    is_bottom: bool = False
+    num_classes: int = 10
+    beta: float = 1.0
+    momentum: float = 0.9
+    weight_decay: float = 5e-4
+    bn_eps: float = 1e-5
+    bn_momentum: float = 0.1
+    lr: float = 0.1          # not part of the descriptor: passed to every update call
+    name: str = ""
+
+    @property
+    def is_top(self) -> bool:
+        return bool(self.layers) and self.layers[-1].is_head
+
+    def input_shape(self) -> Tuple[int, int, int, int]:
+        return (self.n, self.c_in, self.h_in, self.w_in)
+
+    def activation_shapes(self) -> List[Tuple[int, int, int, int]]:
+        """NCHW shape after every non-head layer, in order."""
+        out = []
+        c, h, w = self.c_in, self.h_in, self.w_in
+        for L in self.layers:
+            if L.is_head:
+                break
+            assert L.c_in == c, (L, c)
+            h = (h - 1) // L.stride + 1
+            w = (w - 1) // L.stride + 1
+            c = L.c_out
+            out.append((self.n, c, h, w))
+        return out
+
+    def output_shape(self) -> Tuple[int, ...]:
+        if self.is_top:
+            return (1 + self.n * self.num_classes,)
+        return self.activation_shapes()[-1]
+
+
+def param_shapes(spec: ModuleSpec) -> List[Tuple[str, Tuple[int, ...], str]]:
+    """(name, shape, role) of every parameter tensor in the flat order of the C ABI.
+
+    role is one of 'conv', 'gamma', 'beta', 'fc_w', 'fc_b' and only selects how the synthetic
+    initial value is drawn."""
+    out = []
+    for i, L in enumerate(spec.layers):
+        p = f"L{i}."
+        if L.kind == STEM:
+            out += [(p + "conv.w", (L.c_out, L.c_in, 3, 3), "conv"),
+                    (p + "bn.gamma", (L.c_out,), "gamma"), (p + "bn.beta", (L.c_out,), "beta")]
+        elif L.kind == BASIC_POSTACT:
+            out += [(p + "conv1.w", (L.c_out, L.c_in, 3, 3), "conv"),
+                    (p + "bn1.gamma", (L.c_out,), "gamma"), (p + "bn1.beta", (L.c_out,), "beta"),
+                    (p + "conv2.w", (L.c_out, L.c_out, 3, 3), "conv"),
+                    (p + "bn2.gamma", (L.c_out,), "gamma"), (p + "bn2.beta", (L.c_out,), "beta")]
+            if L.projects:
+                out += [(p + "proj.w", (L.c_out, L.c_in, 1, 1), "conv"),
+                        (p + "bnp.gamma", (L.c_out,), "gamma"), (p + "bnp.beta", (L.c_out,), "beta")]
+        elif L.kind == BASIC_PREACT:
+            out += [(p + "bn1.gamma", (L.c_in,), "gamma"), (p + "bn1.beta", (L.c_in,), "beta"),
+                    (p + "conv1.w", (L.c_out, L.c_in, 3, 3), "conv"),
+                    (p + "bn2.gamma", (L.c_out,), "gamma"), (p + "bn2.beta", (L.c_out,), "beta"),
+                    (p + "conv2.w", (L.c_out, L.c_out, 3, 3), "conv")]
+            if L.projects:
+                out += [(p + "proj.w", (L.c_out, L.c_in, 1, 1), "conv")]
+        elif L.kind == HEAD_POSTACT:
+            out += [(p + "fc.w", (spec.num_classes, L.c_in), "fc_w"), (p + "fc.b", (spec.num_classes,), "fc_b")]
+        elif L.kind == HEAD_PREACT:
+            out += [(p + "bn.gamma", (L.c_in,), "gamma"), (p + "bn.beta", (L.c_in,), "beta"),
+                    (p + "fc.w", (spec.num_classes, L.c_in), "fc_w"), (p + "fc.b", (spec.num_classes,), "fc_b")]
+        else:
+            raise ValueError(f"unknown layer kind {L.kind}")
+    return out
+
+
+def param_count(spec: ModuleSpec) -> int:
+    return int(sum(int(np.prod(s)) for _, s, _ in param_shapes(spec)))
+
+
+# ----------------------------------------------------------------------------------------------
+# seeded tensors
+# ----------------------------------------------------------------------------------------------
+_STREAM_PARAMS = 1 << 20      # + parameter tensor index
+_STREAM_X = 2 << 20           # + step
+_STREAM_G = 3 << 20           # + step
+_STREAM_LABELS = 4 << 20      # + step
+
+
+def _rng(seed: int, stream: int) -> np.random.Generator:
+    return np.random.Generator(np.random.Philox(key=[np.uint64(seed), np.uint64(stream)]))
+
+
+def normal(seed: int, stream: int, shape: Sequence[int], sigma: float = 1.0) -> np.ndarray:
+    """fp32 N(0, sigma^2) tensor of the given shape from stream (seed, stream)."""
+    z = _rng(seed, stream).standard_normal(size=tuple(shape), dtype=np.float32)
+    if sigma != 1.0:
+        z *= np.float32(sigma)
+    return z
+
+
+def make_params(spec: ModuleSpec, seed: int = 0, perturb_bn: bool = False) -> np.ndarray:
+    """Flat fp32 initial parameters: convolutions He-normal with fan-in (sigma = sqrt(2/(c_in*k*k))),
+    FC weights N(0, 1/c_in), FC bias 0, BN gamma 1 and beta 0.  With perturb_bn the BN parameters are
+    moved off their symmetric start (gamma ~ 1 + 0.2 N(0,1), beta ~ 0.2 N(0,1)) so that tests also
+    see non-trivial scale and shift."""
+    chunks = []
+    for idx, (_, shape, role) in enumerate(param_shapes(spec)):
+        stream = _STREAM_PARAMS + idx
+        if role == "conv":
+            fan_in = shape[1] * shape[2] * shape[3]
+            t = normal(seed, stream, shape, float(np.sqrt(2.0 / fan_in)))
+        elif role == "fc_w":
+            t = normal(seed, stream, shape, float(np.sqrt(1.0 / shape[1])))
+        elif role == "fc_b":
+            t = np.zeros(shape, np.float32)
+        elif role == "gamma":
+            t = np.ones(shape, np.float32)
+            if perturb_bn:
+                t = t + normal(seed, stream, shape, 0.2)
+        elif role == "beta":
+            t = np.zeros(shape, np.float32)
+            if perturb_bn:
+                t = t + normal(seed, stream, shape, 0.2)
+        else:
+            raise ValueError(role)
+        chunks.append(t.reshape(-1).astype(np.float32))
+    return np.concatenate(chunks) if chunks else np.zeros(0, np.float32)
+
+
+def make_input(spec: ModuleSpec, step: int, seed: int = 0) -> np.ndarray:
+    """Module input of iteration `step`: fp32 N(0,1), NCHW."""
+    return normal(seed, _STREAM_X + step, spec.input_shape())
+
+
+def make_grad_out(spec: ModuleSpec, step: int, seed: int = 0) -> Optional[np.ndarray]:
+    """Gradient received from the module above for the batch of iteration `step`: fp32 N(0, 1e-2)
+    (sigma 0.1) in the shape of the module output; None for a top module."""
+    if spec.is_top:
+        return None
+    return normal(seed, _STREAM_G + step, spec.output_shape(), 0.1)
+
+
+def make_labels(spec: ModuleSpec, step: int, seed: int = 0) -> Optional[np.ndarray]:
+    """int32 labels uniform in [0, num_classes) for a top module, else None."""
+    if not spec.is_top:
+        return None
+    return _rng(seed, _STREAM_LABELS + step).integers(0, spec.num_classes, size=(spec.n,), dtype=np.int32)
+
+
+# ----------------------------------------------------------------------------------------------
+# the five benchmark configurations
+# ----------------------------------------------------------------------------------------------
+def _postact_stage(c_in: int, c_out: int, blocks: int, first_stride: int) -> List[Layer]:
+    ls = [Layer(BASIC_POSTACT, c_in, c_out, first_stride)]
+    ls += [Layer(BASIC_POSTACT, c_out, c_out, 1) for _ in range(blocks - 1)]
+    return ls
+
+
+def config(idx: int, n: Optional[int] = None) -> ModuleSpec:
+    """Benchmark configuration idx in 1..5.  `n` overrides the batch size (for bounded CPU timing and
+    small parity cases); everything else keeps its real shape."""
+    hyper = dict(momentum=0.9, weight_decay=5e-4, bn_eps=1e-5, bn_momentum=0.1, lr=0.1)
+    if idx == 1:
+        # one post-activation basic block 16->16 on [16,16,32,32]; K=2, module 0, d=1, beta=0.2.
+        # grad_in is computed here although the paper's bottom module has no use for it, so that the
+        # parity test also covers the input gradient of a basic block.
+        return ModuleSpec(n or 16, 16, 32, 32, [Layer(BASIC_POSTACT, 16, 16, 1)], delay=1, is_bottom=False,
+                          beta=0.2, name="cfg1 basic block 16->16", **hyper)
+    if idx == 2:
+        # ResNet-56 module 0 (K=2): stem + all 27 blocks, widths 16/32/64.
+        ls = [Layer(STEM, 3, 16, 1)] + _postact_stage(16, 16, 9, 1) + _postact_stage(16, 32, 9, 2) \
+            + _postact_stage(32, 64, 9, 2)
+        return ModuleSpec(n or 128, 3, 32, 32, ls, delay=1, is_bottom=True, beta=0.2,
+                          name="cfg2 ResNet-56 module 0 (stem + 27 blocks)", **hyper)
+    if idx == 3:
+        # ResNet-110 K=4 module 0: stem + 13 blocks at 16 channels, history depth 3.
+        ls = [Layer(STEM, 3, 16, 1)] + _postact_stage(16, 16, 13, 1)
+        return ModuleSpec(n or 128, 3, 32, 32, ls, delay=3, is_bottom=True, beta=0.2,
+                          name="cfg3 ResNet-110 K=4 module 0 (stem + 13 blocks)", **hyper)
+    if idx == 4:
+        # WRN-28-10 K=2 top module: pre-activation blocks 7..12 (2 x 320 at 16x16, then 320->640
+        # stride 2 and 3 x 640 at 8x8) + BN/ReLU/avgpool/FC/softmax-CE.  d=0, gradient not shrunk.
+        ls = [Layer(BASIC_PREACT, 320, 320, 1), Layer(BASIC_PREACT, 320, 320, 1),
+              Layer(BASIC_PREACT, 320, 640, 2)] + [Layer(BASIC_PREACT, 640, 640, 1) for _ in range(3)] \
+            + [Layer(HEAD_PREACT, 640)]
+        return ModuleSpec(n or 128, 320, 16, 16, ls, delay=0, is_bottom=False, beta=1.0, num_classes=10,
+                          name="cfg4 WRN-28-10 K=2 top module (blocks 7-12 + head)", **hyper)
+    if idx == 5:
+        # ResNet-1202 K=4 module 1: blocks 150..299 = 50 x 16ch at 32x32, 16->32 stride 2, 99 x 32ch.
+        ls = [Layer(BASIC_POSTACT, 16, 16, 1) for _ in range(50)] + _postact_stage(16, 32, 100, 2)
+        return ModuleSpec(n or 128, 16, 32, 32, ls, delay=2, is_bottom=False, beta=0.2,
+                          name="cfg5 ResNet-1202 K=4 module 1 (blocks 150-299)", **hyper)
+    raise ValueError("config index must be 1..5")
+
+
+def conv_flops(spec: ModuleSpec) -> int:
+    """Useful multiply-add flops (2 per MAC) of one module step: forward + data gradient + weight
+    gradient of every convolution and FC; the first layer's data gradient is not counted for a bottom
+    module.  Counting only; no arithmetic of the method."""
+    total = 0
+    c, h, w = spec.c_in, spec.h_in, spec.w_in
+    first = True
+    for L in spec.layers:
+        if L.is_head:
+            total += 3 * 2 * spec.n * c * spec.num_classes
+            break
+        ho, wo = (h - 1) // L.stride + 1, (w - 1) // L.stride + 1
+        m = spec.n * ho * wo
+        convs = []
+        if L.kind == STEM:
+            convs.append((L.c_in, L.c_out, 9, True))
+        else:
+            convs.append((L.c_in, L.c_out, 9, True))
+            convs.append((L.c_out, L.c_out, 9, False))
+            if L.projects:
+                convs.append((L.c_in, L.c_out, 1, True))
+        for ci, co, taps, reads_module_input in convs:
+            f = 2 * m * ci * co * taps
+            passes = 3
+            if first and reads_module_input and spec.is_bottom and L.kind in (STEM, BASIC_POSTACT):
+                passes = 2
+            total += passes * f
+        first = False
+        c, h, w = L.c_out, ho, wo
+    return total

@@ -1,0 +1,168 @@
+/*
+ * fdg.h -- C ABI of one FDG module worker on one MI355X (gfx950).
+ *
+ * FDG (fully decoupled learning with delayed gradients, arXiv 1906.09108) splits a network into K
+ * modules.  Section III-A of the paper states what one module does per iteration:
+ *   forward   : run the module's layers on the newest input and keep what the later backward needs
+ *               (the "saved computation graph" of Fig. 1(b));
+ *   backward  : resume back-propagation on an OLDER batch with the gradient received from the
+ *               module above, every factor evaluated at that older batch (Eq. 10), after the
+ *               gradient was multiplied by the shrinking factor beta (Eq. 15);
+ *   update    : apply the resulting delayed gradient to the CURRENT weights (Eq. 11 / Eq. 12).
+ * This library is that worker.  A module is a list of ResNet-style layers; the history of saved
+ * forwards is a FIFO ring of delay+1 contexts.
+ *
+ * Conventions that hold for every entry point
+ *   - Pointers named *_dev are DEVICE pointers (HBM); pointers named host_* are HOST pointers.
+ *   - Boundary tensors are fp32, NCHW, dense.
+ *   - The caller owns every device buffer, including the single workspace arena given at create.
+ *     The library never allocates or frees device memory; fdg_destroy frees only the host object.
+ *   - `hip_stream` is a hipStream_t cast to void* (NULL = the null stream).  All device work of a
+ *     call is enqueued on it and the call returns without waiting, except the host accessors
+ *     (fdg_get_*, fdg_set_params) which synchronise that module's last used stream.
+ *   - Errors are status codes; nothing throws or aborts.  Argument and queue errors are detected
+ *     before anything is enqueued, so a failed call leaves the module unchanged.
+ *   - A module object is not thread safe; calls on one module must be serialised by the caller.
+ */
+#ifndef FDG_H_
+#define FDG_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fdg_module fdg_module; /* opaque, host memory, library-owned */
+
+typedef enum {
+  FDG_OK = 0,
+  FDG_ERR_INVALID_ARG = 1,         /* NULL where a pointer is required, bad descriptor, bad count */
+  FDG_ERR_UNSUPPORTED = 2,         /* a layer shape this build has no kernel for */
+  FDG_ERR_WORKSPACE_TOO_SMALL = 3, /* bytes < fdg_module_workspace_bytes(desc) or misaligned */
+  FDG_ERR_QUEUE_FULL = 4,          /* forward with delay+1 contexts outstanding */
+  FDG_ERR_QUEUE_EMPTY = 5,         /* backward with no context outstanding */
+  FDG_ERR_NO_GRAD = 6,             /* update with no backward since the last update */
+  FDG_ERR_HIP = 7                  /* a HIP call or kernel launch failed */
+} fdg_status;
+
+/* Layer kinds.  All convolutions are bias-free.  BN = training-mode batch normalisation.
+ *   STEM_CONV_BN_RELU : conv3x3(c_in->c_out, stride) -> BN -> ReLU
+ *   BASIC_POSTACT     : conv3x3(stride) -> BN -> ReLU -> conv3x3 -> BN -> (+shortcut) -> ReLU,
+ *                       shortcut = identity, or conv1x1(stride)+BN when stride!=1 or c_in!=c_out
+ *   BASIC_PREACT      : o=ReLU(BN(x)); conv3x3(o,stride) -> BN -> ReLU -> conv3x3, + shortcut,
+ *                       shortcut = x, or conv1x1(o, stride) when stride!=1 or c_in!=c_out
+ *   HEAD_POSTACT      : global average pool -> FC(c_in->num_classes)+bias -> softmax cross-entropy
+ *   HEAD_PREACT       : BN -> ReLU -> the same head
+ * A head, if present, must be the last layer; the module is then a TOP module (Section III-B:
+ * its gradient is not shrunk and it needs no gradient from above).                              */
+typedef enum {
+  FDG_STEM_CONV_BN_RELU = 0,
+  FDG_BASIC_POSTACT = 1,
+  FDG_BASIC_PREACT = 2,
+  FDG_HEAD_POSTACT = 3,
+  FDG_HEAD_PREACT = 4
+} fdg_layer_kind;
+
+typedef struct {
+  int32_t kind;   /* fdg_layer_kind */
+  int32_t c_in;   /* input channels; must equal the previous layer's c_out */
+  int32_t c_out;  /* output channels (heads: ignored, num_classes is used) */
+  int32_t stride; /* 1 or 2 (heads: ignored) */
+} fdg_layer_desc;
+
+typedef struct {
+  int32_t n, c_in, h_in, w_in;  /* module input shape, NCHW */
+  int32_t num_layers;
+  const fdg_layer_desc* layers; /* HOST pointer; copied at create */
+  int32_t delay;                /* d >= 0: the ring holds d+1 saved forwards */
+  int32_t is_bottom;            /* 1: the gradient of the module input is never computed */
+  int32_t num_classes;          /* heads only */
+  float beta;                   /* gradient shrinking factor of Eq. 15, 0 < beta <= 1 */
+  float momentum;               /* SGD momentum mu */
+  float weight_decay;           /* L2 coefficient added to the gradient of every parameter */
+  float bn_eps;                 /* added to the batch variance */
+  float bn_momentum;            /* running-statistics momentum */
+} fdg_module_desc;
+
+/* Bytes of device workspace a module of this shape needs (parameters, momentum, gradients, the
+ * ring of saved forwards with their bf16 weight snapshots, temporaries).  0 on an invalid or
+ * unsupported descriptor.  The arena must be aligned to 256 bytes.                               */
+size_t fdg_module_workspace_bytes(const fdg_module_desc* desc);
+
+/* Build the host object over `dev_workspace` (DEVICE memory, `bytes` long, caller-owned, must
+ * outlive the module).  Parameters, momentum, gradients and running statistics start at zero
+ * (running variance at one); call fdg_set_params before the first forward.  Enqueues the zero
+ * fill on `hip_stream`.                                                                          */
+fdg_status fdg_module_create(const fdg_module_desc* desc, void* dev_workspace, size_t bytes,
+                             void* hip_stream, fdg_module** out);
+
+/* Forward step of Section III-A: run the layers on x with the CURRENT weights and push a context
+ * (saved activations, batch statistics, and a snapshot of the weights used) into the ring.
+ *   x_dev      : [n, c_in, h_in, w_in] fp32 NCHW, read only.
+ *   labels_dev : [n] int32 class ids in [0, num_classes) for a top module, else NULL.
+ *   y_dev      : output.  Non-top: [n, c_out, h_out, w_out] fp32 NCHW.  Top: 1 + n*num_classes
+ *                floats = mean loss followed by the logits, row major [n][num_classes].
+ * FDG_ERR_QUEUE_FULL if delay+1 contexts are outstanding.                                       */
+fdg_status fdg_forward(fdg_module* m, const float* x_dev, const int32_t* labels_dev, float* y_dev,
+                       void* hip_stream);
+
+/* Delayed backward of Eq. 10 with the shrinking of Eq. 15: pops the OLDEST context, multiplies
+ * grad_out by beta, back-propagates through that context's saved activations and weight
+ * snapshot, leaves the parameter gradient in the module (fdg_get_grads) and, unless is_bottom or
+ * grad_in_dev is NULL, writes the gradient of the module input (it carries this module's beta,
+ * so a chain of modules compounds to beta^(K-k), Eq. 16).
+ *   grad_out_dev : same shape as the forward's y, fp32 NCHW.  Must be NULL for a top module
+ *                  (its gradient starts at the loss inside the module).
+ *   grad_in_dev  : [n, c_in, h_in, w_in] fp32 NCHW or NULL.
+ * FDG_ERR_QUEUE_EMPTY if nothing is outstanding.                                                */
+fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float* grad_in_dev,
+                                void* hip_stream);
+
+/* Update of Eq. 11 / Eq. 12 on the CURRENT parameters with the last delayed gradient g:
+ *   g' = g + weight_decay*theta;  v = momentum*v + g';  theta = theta - lr*v
+ * (momentum, weight decay: Section V-A).  FDG_ERR_NO_GRAD if no backward ran since the last
+ * update.                                                                                       */
+fdg_status fdg_update(fdg_module* m, float lr, void* hip_stream);
+
+/* Frees the host object only (NULL is allowed).  The workspace stays with the caller. */
+void fdg_destroy(fdg_module* m);
+
+/* ---- host accessors (parity, checkpointing).  Flat parameter order: layers in order; inside a
+ * layer the tensors in this order, each row major in its stated shape:
+ *   STEM          : conv w[c_out,c_in,3,3], bn gamma[c_out], bn beta[c_out]
+ *   BASIC_POSTACT : conv1 w[c_out,c_in,3,3], bn1 gamma, bn1 beta, conv2 w[c_out,c_out,3,3],
+ *                   bn2 gamma, bn2 beta, then if projecting: proj w[c_out,c_in,1,1], bnp gamma,
+ *                   bnp beta
+ *   BASIC_PREACT  : bn1 gamma[c_in], bn1 beta[c_in], conv1 w[c_out,c_in,3,3], bn2 gamma[c_out],
+ *                   bn2 beta[c_out], conv2 w[c_out,c_out,3,3], then if projecting:
+ *                   proj w[c_out,c_in,1,1]
+ *   HEAD_POSTACT  : fc W[num_classes,c_in], fc b[num_classes]
+ *   HEAD_PREACT   : bn gamma[c_in], bn beta[c_in], fc W, fc b
+ * `count` must equal fdg_param_count.                                                           */
+size_t fdg_param_count(const fdg_module* m);
+fdg_status fdg_set_params(fdg_module* m, const float* host_src, size_t count); /* momentum := 0 */
+fdg_status fdg_get_params(const fdg_module* m, float* host_dst, size_t count);
+fdg_status fdg_get_grads(const fdg_module* m, float* host_dst, size_t count); /* beta-scaled, before weight decay */
+fdg_status fdg_get_momentum(const fdg_module* m, float* host_dst, size_t count);
+
+/* Running BN statistics, flat: for every BN in the parameter order above, mean[c] then var[c]. */
+size_t fdg_bn_stat_count(const fdg_module* m);
+fdg_status fdg_get_bn_running(const fdg_module* m, float* host_dst, size_t count);
+
+/* Shape of the forward's y: out[0..3] = n, c, h, w (top module: 1, 1, 1, 1 + n*num_classes). */
+fdg_status fdg_output_shape(const fdg_module* m, int32_t out[4]);
+
+/* Ring state: number of outstanding contexts and the sequence numbers (0-based count of forwards)
+ * of the oldest and newest one (-1 when empty).  Any of the three output pointers may be NULL.
+ * A forward with sequence number s is stored in ring slot s mod (delay+1).                       */
+fdg_status fdg_queue_state(const fdg_module* m, int32_t* outstanding, int64_t* oldest_seq,
+                           int64_t* newest_seq);
+
+const char* fdg_status_string(fdg_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FDG_H_ */

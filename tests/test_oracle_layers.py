@@ -1,0 +1,228 @@
+"""Pins for the layer arithmetic of the CPU oracle (oracle/fdg_oracle_kernels.c).
+
+The paper names its layers only by architecture, so each routine is pinned to what mathematics and
+independent libraries fix: scipy's correlate2d, torch's CPU operators and autograd, closed forms,
+adjoint identities, finite differences in float64 and brute-force Python loops on tiny inputs."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+import scipy.signal
+import torch
+import torch.nn.functional as F
+
+from oracle.fdg_oracle import Kernels
+
+K64 = Kernels(np.float64)
+K32 = Kernels(np.float32)
+rng = np.random.default_rng(1234)
+
+
+def rnd(*shape):
+    return rng.standard_normal(shape)
+
+
+CONV_CASES = [  # N, Ci, H, W, Co, k, stride, pad
+    (2, 3, 5, 5, 4, 3, 1, 1),
+    (2, 4, 6, 7, 3, 3, 2, 1),
+    (1, 2, 5, 4, 5, 3, 2, 1),
+    (3, 4, 6, 6, 2, 1, 1, 0),
+    (2, 3, 7, 5, 4, 1, 2, 0),
+    (2, 3, 8, 8, 4, 1, 2, 0),
+]
+
+
+def brute_conv(x, w, s, p):
+    N, Ci, H, W = x.shape
+    Co, _, k, _ = w.shape
+    Ho, Wo = (H + 2 * p - k) // s + 1, (W + 2 * p - k) // s + 1
+    y = np.zeros((N, Co, Ho, Wo))
+    for n, co, ho, wo, ci, r, q in itertools.product(range(N), range(Co), range(Ho), range(Wo), range(Ci),
+                                                    range(k), range(k)):
+        h, ww = ho * s + r - p, wo * s + q - p
+        if 0 <= h < H and 0 <= ww < W:
+            y[n, co, ho, wo] += x[n, ci, h, ww] * w[co, ci, r, q]
+    return y
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_fwd_brute_force(case):
+    N, Ci, H, W, Co, k, s, p = case
+    x, w = rnd(N, Ci, H, W), rnd(Co, Ci, k, k)
+    np.testing.assert_allclose(K64.conv_fwd(x, w, s, p), brute_conv(x, w, s, p), rtol=1e-12, atol=1e-12)
+
+
+def test_conv_fwd_is_scipy_correlation():
+    """3x3, pad 1, stride 1 is a 'same' cross-correlation summed over input channels; stride 2 keeps
+    every second output of it."""
+    x, w = rnd(2, 3, 8, 6), rnd(4, 3, 3, 3)
+    full = np.zeros((2, 4, 8, 6))
+    for n, co, ci in itertools.product(range(2), range(4), range(3)):
+        full[n, co] += scipy.signal.correlate2d(x[n, ci], w[co, ci], mode="same", boundary="fill")
+    np.testing.assert_allclose(K64.conv_fwd(x, w, 1, 1), full, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(K64.conv_fwd(x, w, 2, 1), full[:, :, ::2, ::2], rtol=1e-12, atol=1e-12)
+
+
+def test_conv_1x1_is_matmul():
+    x, w = rnd(3, 5, 6, 4), rnd(7, 5, 1, 1)
+    np.testing.assert_allclose(K64.conv_fwd(x, w, 1, 0), np.einsum("nchw,oc->nohw", x, w[:, :, 0, 0]), rtol=1e-12)
+    np.testing.assert_allclose(K64.conv_fwd(x, w, 2, 0),
+                               np.einsum("nchw,oc->nohw", x[:, :, ::2, ::2], w[:, :, 0, 0]), rtol=1e-12)
+
+
+def test_conv_delta_kernel_shifts():
+    """A kernel that is 1 at tap (r,q) of channel c->c copies the image shifted by (r-1, q-1)."""
+    x = rnd(1, 2, 5, 5)
+    for r, q in itertools.product(range(3), range(3)):
+        w = np.zeros((2, 2, 3, 3))
+        w[0, 0, r, q] = w[1, 1, r, q] = 1.0
+        y = K64.conv_fwd(x, w, 1, 1)
+        xp = np.pad(x, ((0, 0), (0, 0), (1, 1), (1, 1)))
+        np.testing.assert_array_equal(y, xp[:, :, r:r + 5, q:q + 5])
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_adjoint_identities(case):
+    """<conv(x,w), g> = <x, dgrad(g,w)> = <w, wgrad(x,g)> because conv is bilinear."""
+    N, Ci, H, W, Co, k, s, p = case
+    x, w = rnd(N, Ci, H, W), rnd(Co, Ci, k, k)
+    y = K64.conv_fwd(x, w, s, p)
+    g = rnd(*y.shape)
+    lhs = float((y * g).sum())
+    assert math.isclose(lhs, float((x * K64.conv_bwd_data(g, w, x.shape, s, p)).sum()), rel_tol=1e-11, abs_tol=1e-11)
+    assert math.isclose(lhs, float((w * K64.conv_bwd_weight(x, g, k, s, p)).sum()), rel_tol=1e-11, abs_tol=1e-11)
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_against_torch_autograd(case):
+    N, Ci, H, W, Co, k, s, p = case
+    x, w = rnd(N, Ci, H, W), rnd(Co, Ci, k, k)
+    xt, wt = torch.tensor(x, requires_grad=True), torch.tensor(w, requires_grad=True)
+    yt = F.conv2d(xt, wt, stride=s, padding=p)
+    g = rnd(*yt.shape)
+    yt.backward(torch.tensor(g))
+    np.testing.assert_allclose(K64.conv_fwd(x, w, s, p), yt.detach().numpy(), rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(K64.conv_bwd_data(g, w, x.shape, s, p), xt.grad.numpy(), rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(K64.conv_bwd_weight(x, g, k, s, p), wt.grad.numpy(), rtol=1e-11, atol=1e-12)
+
+
+def test_bn_fwd_closed_form():
+    """Per channel the output has mean beta and variance gamma^2 * var/(var+eps)."""
+    x = rnd(4, 3, 5, 6) * np.array([0.5, 2.0, 7.0]).reshape(1, 3, 1, 1) + np.array([3.0, -1.0, 0.2]).reshape(1, 3, 1, 1)
+    gamma, beta, eps = np.array([1.5, -0.7, 2.0]), np.array([0.3, 0.1, -2.0]), 1e-5
+    y, mean, var, invstd = K64.bn_fwd(x, gamma, beta, eps)
+    np.testing.assert_allclose(mean, x.mean(axis=(0, 2, 3)), rtol=1e-12)
+    np.testing.assert_allclose(var, x.var(axis=(0, 2, 3)), rtol=1e-12)          # biased
+    np.testing.assert_allclose(invstd, 1 / np.sqrt(var + eps), rtol=1e-12)
+    np.testing.assert_allclose(y.mean(axis=(0, 2, 3)), beta, atol=1e-12)
+    np.testing.assert_allclose(y.var(axis=(0, 2, 3)), gamma ** 2 * var / (var + eps), rtol=1e-11)
+
+
+def test_bn_bwd_invariants_and_torch():
+    x, dy = rnd(3, 4, 5, 5) * 2 + 1, rnd(3, 4, 5, 5)
+    gamma, beta, eps = rnd(4) + 2, rnd(4), 1e-5
+    _, mean, var, invstd = K64.bn_fwd(x, gamma, beta, eps)
+    dx, dgamma, dbeta = K64.bn_bwd(x, dy, gamma, mean, invstd)
+    xhat = (x - mean.reshape(1, -1, 1, 1)) * invstd.reshape(1, -1, 1, 1)
+    np.testing.assert_allclose(dx.sum(axis=(0, 2, 3)), 0, atol=1e-11)             # shift invariance
+    # scale invariance, exact form: sum dx*xhat = gamma*invstd*dgamma * eps/(var+eps)
+    np.testing.assert_allclose((dx * xhat).sum(axis=(0, 2, 3)), gamma * invstd * dgamma * eps * invstd ** 2,
+                               rtol=1e-6, atol=1e-12)
+    xt, gt, bt = (torch.tensor(a, requires_grad=True) for a in (x, gamma, beta))
+    yt = F.batch_norm(xt, None, None, gt, bt, training=True, eps=eps)
+    yt.backward(torch.tensor(dy))
+    np.testing.assert_allclose(dx, xt.grad.numpy(), rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(dgamma, gt.grad.numpy(), rtol=1e-10)
+    np.testing.assert_allclose(dbeta, bt.grad.numpy(), rtol=1e-10)
+
+
+def test_bn_bwd_finite_differences():
+    x, dy = rnd(2, 2, 3, 3), rnd(2, 2, 3, 3)
+    gamma, beta, eps = np.array([1.3, 0.6]), np.array([0.1, -0.4]), 1e-5
+    _, mean, var, invstd = K64.bn_fwd(x, gamma, beta, eps)
+    dx, _, _ = K64.bn_bwd(x, dy, gamma, mean, invstd)
+
+    def L(xx):
+        return float((K64.bn_fwd(xx, gamma, beta, eps)[0] * dy).sum())
+    h = 1e-6
+    for idx in [(0, 0, 0, 0), (1, 1, 2, 1), (0, 1, 1, 2)]:
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += h
+        xm[idx] -= h
+        assert math.isclose((L(xp) - L(xm)) / (2 * h), dx[idx], rel_tol=1e-6, abs_tol=1e-8)
+
+
+def test_relu():
+    x = np.array([-2.0, -0.0, 0.0, 1e-9, 3.0])
+    np.testing.assert_array_equal(K64.relu_fwd(x), [0, 0, 0, 1e-9, 3.0])
+    np.testing.assert_array_equal(K64.relu_bwd(x, np.ones(5)), [0, 0, 0, 1, 1])   # derivative 0 at 0
+
+
+def test_avgpool_and_fc_against_numpy_and_torch():
+    x = rnd(3, 4, 2, 5)
+    np.testing.assert_allclose(K64.avgpool_fwd(x), x.mean(axis=(2, 3)), rtol=1e-12)
+    dp = rnd(3, 4)
+    np.testing.assert_allclose(K64.avgpool_bwd(dp, x.shape), np.broadcast_to(dp[:, :, None, None] / 10, x.shape), rtol=1e-12)
+    p, Wt, b, dl = rnd(3, 4), rnd(6, 4), rnd(6), rnd(3, 6)
+    np.testing.assert_allclose(K64.fc_fwd(p, Wt, b), p @ Wt.T + b, rtol=1e-12)
+    dWt, db, dpp = K64.fc_bwd(p, Wt, dl)
+    np.testing.assert_allclose(dWt, dl.T @ p, rtol=1e-12)
+    np.testing.assert_allclose(db, dl.sum(0), rtol=1e-12)
+    np.testing.assert_allclose(dpp, dl @ Wt, rtol=1e-12)
+
+
+def test_softmax_ce_closed_forms():
+    N, J = 5, 10
+    labels = np.array([0, 3, 9, 3, 1], np.int32)
+    loss, dl = K64.softmax_ce(np.full((N, J), 2.5), labels)      # uniform logits -> ln J
+    assert math.isclose(loss, math.log(J), rel_tol=1e-12)
+    logits = rnd(N, J) * 3
+    loss, dl = K64.softmax_ce(logits, labels)
+    np.testing.assert_allclose(dl.sum(axis=1), 0, atol=1e-15)    # rows of the gradient sum to zero
+    lt = torch.tensor(logits, requires_grad=True)
+    lo = F.cross_entropy(lt, torch.tensor(labels, dtype=torch.long))
+    lo.backward()
+    assert math.isclose(loss, lo.item(), rel_tol=1e-12)
+    np.testing.assert_allclose(dl, lt.grad.numpy(), rtol=1e-10, atol=1e-14)
+    # shift invariance and no overflow for huge logits
+    loss2, _ = K64.softmax_ce(logits + 1000.0, labels)
+    assert math.isclose(loss, loss2, rel_tol=1e-9)
+
+
+def test_sgd_momentum_closed_forms():
+    """Constant gradient c, no decay: v_n = c(1-mu^n)/(1-mu), theta_n = theta_0 - lr*sum v_i.
+    Decay only, no momentum: theta_n = theta_0 (1 - lr*wd)^n."""
+    mu, lr, c, n = 0.9, 0.1, 0.25, 7
+    theta, v, g = np.array([1.0, -2.0]), np.zeros(2), np.full(2, c)
+    for _ in range(n):
+        K64.sgd_momentum(theta, v, g, lr, mu, 0.0)
+    vs = [c * (1 - mu ** i) / (1 - mu) for i in range(1, n + 1)]
+    np.testing.assert_allclose(v, vs[-1], rtol=1e-12)
+    np.testing.assert_allclose(theta, np.array([1.0, -2.0]) - lr * sum(vs), rtol=1e-12)
+    theta, v = np.array([1.0, -2.0]), np.zeros(2)
+    for _ in range(n):
+        K64.sgd_momentum(theta, v, np.zeros(2), lr, 0.0, 5e-4)
+    np.testing.assert_allclose(theta, np.array([1.0, -2.0]) * (1 - lr * 5e-4) ** n, rtol=1e-12)
+
+
+def test_sgd_against_torch_optimizer():
+    p0, g = rnd(50), [rnd(50) for _ in range(4)]
+    tp = torch.nn.Parameter(torch.tensor(p0))
+    opt = torch.optim.SGD([tp], lr=0.1, momentum=0.9, weight_decay=5e-4)
+    theta, v = p0.copy(), np.zeros(50)
+    for gi in g:
+        tp.grad = torch.tensor(gi)
+        opt.step()
+        K64.sgd_momentum(theta, v, gi, 0.1, 0.9, 5e-4)
+    np.testing.assert_allclose(theta, tp.detach().numpy(), rtol=1e-12)
+
+
+def test_float32_build_matches_float64_build():
+    x, w = rnd(2, 8, 6, 6), rnd(8, 8, 3, 3)
+    np.testing.assert_allclose(K32.conv_fwd(x, w, 1, 1), K64.conv_fwd(x, w, 1, 1), rtol=1e-4, atol=1e-5)
+    g = rnd(2, 8, 6, 6)
+    np.testing.assert_allclose(K32.conv_bwd_weight(x, g, 3, 1, 1), K64.conv_bwd_weight(x, g, 3, 1, 1), rtol=1e-4, atol=1e-5)
+    np.testing.assert_allclose(K32.conv_bwd_data(g, w, x.shape, 1, 1), K64.conv_bwd_data(g, w, x.shape, 1, 1), rtol=1e-4, atol=1e-5)
+    y32, y64 = K32.bn_fwd(x, np.ones(8), np.zeros(8), 1e-5)[0], K64.bn_fwd(x, np.ones(8), np.zeros(8), 1e-5)[0]
+    np.testing.assert_allclose(y32, y64, rtol=1e-4, atol=1e-5)

@@ -1,0 +1,279 @@
+"""Pins for the module-level oracle (oracle/fdg_oracle.py): what the paper fixes about one FDG module.
+
+ * Eq. 8-10: inside a module the backward is the chain rule -> whole-module gradients against central
+   finite differences in float64 and against torch.autograd on an independent torch model.
+ * K=1 / d=0 / beta=1 is standard back-propagation: a net split into K lock-step modules gives the
+   gradients and the post-update weights of the unsplit net.
+ * Section III-A: the delayed backward uses the activations AND weights of the stale batch: it equals
+   a fresh back-propagation at (x_stale, theta_snapshot), times beta (Eq. 15).
+ * Eq. 15-17: beta enters linearly; a chain of modules compounds to beta^(K-k); beta=1 is a no-op.
+ * Eq. 11/12: the update moves the CURRENT weights with the delayed gradient.
+"""
+import copy
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import fdg_workloads as W
+from fdg_workloads import Layer, ModuleSpec
+from oracle.fdg_oracle import NoGrad, OracleModule, QueueEmpty, QueueFull
+from tests import torch_ref
+
+TINY = {
+    "stem": ModuleSpec(2, 3, 6, 6, [Layer(W.STEM, 3, 4, 1)], is_bottom=False),
+    "postact_identity": ModuleSpec(2, 4, 5, 5, [Layer(W.BASIC_POSTACT, 4, 4, 1)]),
+    "postact_project": ModuleSpec(2, 4, 6, 6, [Layer(W.BASIC_POSTACT, 4, 6, 2)]),
+    "preact_identity": ModuleSpec(2, 4, 5, 5, [Layer(W.BASIC_PREACT, 4, 4, 1)]),
+    "preact_project": ModuleSpec(2, 4, 6, 6, [Layer(W.BASIC_PREACT, 4, 6, 2)]),
+    "preact_widen": ModuleSpec(2, 4, 5, 5, [Layer(W.BASIC_PREACT, 4, 6, 1)]),
+    "head_preact": ModuleSpec(3, 4, 4, 4, [Layer(W.BASIC_PREACT, 4, 4, 1), Layer(W.HEAD_PREACT, 4)], num_classes=5),
+    "head_postact": ModuleSpec(3, 4, 4, 4, [Layer(W.BASIC_POSTACT, 4, 4, 1), Layer(W.HEAD_POSTACT, 4)], num_classes=5),
+    "stack": ModuleSpec(2, 3, 8, 8, [Layer(W.STEM, 3, 4, 1), Layer(W.BASIC_POSTACT, 4, 4, 1),
+                                    Layer(W.BASIC_POSTACT, 4, 8, 2), Layer(W.BASIC_POSTACT, 8, 8, 1)]),
+}
+
+
+def _inputs(spec, seed=3):
+    theta = W.make_params(spec, seed, perturb_bn=True).astype(np.float64)
+    x = W.make_input(spec, 0, seed).astype(np.float64)
+    g = W.make_grad_out(spec, 0, seed)
+    g = None if g is None else g.astype(np.float64) * 10
+    labels = W.make_labels(spec, 0, seed)
+    return theta, x, g, labels
+
+
+@pytest.mark.parametrize("name", list(TINY))
+def test_layouts_agree(name):
+    spec = TINY[name]
+    m = OracleModule(spec)
+    assert [(n.split(".", 1)[1], s) for n, s in m.layout] == [(n.split(".", 1)[1], s) for n, s, _ in W.param_shapes(spec)]
+    assert m.param_count() == W.param_count(spec)
+
+
+@pytest.mark.parametrize("name", list(TINY))
+def test_module_gradient_against_torch_autograd(name):
+    spec = TINY[name]
+    theta, x, g, labels = _inputs(spec)
+    m = OracleModule(spec, np.float64)
+    m.set_params(theta)
+    y = m.forward(x, labels)
+    gin = m.backward_delayed(g)
+    params = torch_ref.split_params(spec, W.param_shapes(spec), theta)
+    xt = torch.tensor(x, requires_grad=True)
+    out = torch_ref.forward(spec, params, xt, labels)
+    if spec.is_top:
+        loss, logits = out
+        assert math.isclose(y[0], loss.item(), rel_tol=1e-10)
+        np.testing.assert_allclose(y[1:], logits.detach().numpy().reshape(-1), rtol=1e-9, atol=1e-11)
+        loss.backward()
+    else:
+        np.testing.assert_allclose(y, out.detach().numpy(), rtol=1e-9, atol=1e-11)
+        out.backward(torch.tensor(g) * spec.beta)
+    ref = np.concatenate([p.grad.numpy().reshape(-1) for p in params])
+    np.testing.assert_allclose(m.get_grads(), ref, rtol=1e-7, atol=1e-10)
+    np.testing.assert_allclose(gin, xt.grad.numpy(), rtol=1e-7, atol=1e-10)
+
+
+@pytest.mark.parametrize("name", list(TINY))
+def test_module_gradient_against_finite_differences(name):
+    """L(theta, x) = <g, module(x; theta)> (loss for a top module); central differences in float64."""
+    spec = TINY[name]
+    theta, x, g, labels = _inputs(spec, seed=5)
+
+    def L(th, xx):
+        mm = OracleModule(spec, np.float64)
+        mm.set_params(th)
+        y = mm.forward(xx, labels)
+        return float(y[0]) if spec.is_top else float((y * g).sum())
+
+    m = OracleModule(spec, np.float64)
+    m.set_params(theta)
+    m.forward(x, labels)
+    gin = m.backward_delayed(g)
+    gth = m.get_grads()
+    r = np.random.default_rng(0)
+    h = 1e-6
+    for i in r.choice(theta.size, size=min(25, theta.size), replace=False):
+        tp, tm = theta.copy(), theta.copy()
+        tp[i] += h
+        tm[i] -= h
+        fd = (L(tp, x) - L(tm, x)) / (2 * h)
+        assert math.isclose(fd, gth[i], rel_tol=2e-5, abs_tol=2e-7), (name, i, fd, gth[i])
+    xf = x.reshape(-1)
+    for i in r.choice(xf.size, size=15, replace=False):
+        xp, xm = xf.copy(), xf.copy()
+        xp[i] += h
+        xm[i] -= h
+        fd = (L(theta, xp.reshape(x.shape)) - L(theta, xm.reshape(x.shape))) / (2 * h)
+        assert math.isclose(fd, gin.reshape(-1)[i], rel_tol=2e-5, abs_tol=2e-7), (name, i, fd, gin.reshape(-1)[i])
+
+
+def _split(spec, cuts, betas, delay=0):
+    """Split spec.layers at the given layer indices into consecutive modules."""
+    mods, shapes = [], [spec.input_shape()] + spec.activation_shapes()
+    bounds = [0] + list(cuts) + [len(spec.layers)]
+    for j in range(len(bounds) - 1):
+        a, b = bounds[j], bounds[j + 1]
+        n, c, h, w = shapes[a]
+        mods.append(ModuleSpec(n, c, h, w, spec.layers[a:b], delay=delay, is_bottom=False, num_classes=spec.num_classes,
+                               beta=betas[j], momentum=spec.momentum, weight_decay=spec.weight_decay))
+    return mods
+
+
+def _net():
+    return ModuleSpec(4, 3, 8, 8, [Layer(W.STEM, 3, 4, 1), Layer(W.BASIC_POSTACT, 4, 4, 1),
+                                   Layer(W.BASIC_POSTACT, 4, 8, 2), Layer(W.BASIC_PREACT, 8, 8, 1),
+                                   Layer(W.HEAD_PREACT, 8)], num_classes=5)
+
+
+@pytest.mark.parametrize("cuts", [(2,), (1, 3), (1, 2, 4)])
+def test_lockstep_split_equals_standard_bp(cuts):
+    """No delay and beta=1: module-wise BP is the chain rule (Eq. 8, Eq. 9), so the split network gives
+    the unsplit network's gradient and, after the update, its weights."""
+    net = _net()
+    theta, x, _, labels = _inputs(net, seed=7)
+    whole = OracleModule(net, np.float64)
+    whole.set_params(theta)
+    y = whole.forward(x, labels)
+    gin = whole.backward_delayed(None)
+    whole.update(0.1)
+    specs = _split(net, cuts, [1.0] * (len(cuts) + 1))
+    mods, off = [], 0
+    for s in specs:
+        m = OracleModule(s, np.float64)
+        m.set_params(theta[off:off + m.param_count()])
+        off += m.param_count()
+        mods.append(m)
+    z = x
+    for m in mods[:-1]:
+        z = m.forward(z)
+    yk = mods[-1].forward(z, labels)
+    np.testing.assert_allclose(yk, y, rtol=1e-12, atol=1e-13)
+    g = mods[-1].backward_delayed(None)
+    for m in reversed(mods[:-1]):
+        g = m.backward_delayed(g)
+    np.testing.assert_allclose(g, gin, rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(np.concatenate([m.get_grads() for m in mods]), whole.get_grads(), rtol=1e-10, atol=1e-13)
+    for m in mods:
+        m.update(0.1)
+    np.testing.assert_allclose(np.concatenate([m.get_params() for m in mods]), whole.get_params(), rtol=1e-12, atol=1e-14)
+
+
+def test_beta_chain_compounds_to_power():
+    """Eq. 16 / Eq. 17: with every non-top module shrinking by beta, module k of K sees beta^(K-k) times
+    the true gradient; the top module is not shrunk."""
+    net, beta = _net(), 0.5
+    theta, x, _, labels = _inputs(net, seed=9)
+    whole = OracleModule(net, np.float64)
+    whole.set_params(theta)
+    whole.forward(x, labels)
+    whole.backward_delayed(None)
+    cuts = (1, 3)
+    K = 3
+    specs = _split(net, cuts, [beta, beta, 1.0])
+    mods, off, ranges = [], 0, []
+    for s in specs:
+        m = OracleModule(s, np.float64)
+        m.set_params(theta[off:off + m.param_count()])
+        ranges.append((off, off + m.param_count()))
+        off += m.param_count()
+        mods.append(m)
+    z = x
+    for m in mods[:-1]:
+        z = m.forward(z)
+    mods[-1].forward(z, labels)
+    g = mods[-1].backward_delayed(None)
+    for m in reversed(mods[:-1]):
+        g = m.backward_delayed(g)
+    for k1, (m, (a, b)) in enumerate(zip(mods, ranges), start=1):
+        np.testing.assert_allclose(m.get_grads(), beta ** (K - k1) * whole.get_grads()[a:b], rtol=1e-10, atol=1e-14)
+
+
+def test_beta_is_linear_and_exact_for_half():
+    spec32 = copy.deepcopy(TINY["stack"])
+    theta, x, g, _ = _inputs(spec32, seed=11)
+    outs = {}
+    for beta in (1.0, 0.5):
+        spec32.beta = beta
+        m = OracleModule(spec32, np.float32)
+        m.set_params(theta)
+        m.forward(x)
+        gin = m.backward_delayed(g)
+        outs[beta] = (m.get_grads(), gin)
+    # multiplying by 0.5 is exact in binary floating point, so the whole linear backward scales exactly
+    np.testing.assert_array_equal(outs[0.5][0], np.float32(0.5) * outs[1.0][0])
+    np.testing.assert_array_equal(outs[0.5][1], np.float32(0.5) * outs[1.0][1])
+
+
+@pytest.mark.parametrize("d", [1, 3])
+def test_delayed_backward_is_fresh_bp_at_stale_batch_and_stale_weights(d):
+    """After d further forwards and updates, the backward of the oldest context equals back-propagation
+    evaluated at (x_stale, theta at that forward), times beta."""
+    spec = copy.deepcopy(TINY["stack"])
+    spec.delay, spec.beta = d, 0.2
+    theta0 = W.make_params(spec, 1, perturb_bn=True).astype(np.float64)
+    m = OracleModule(spec, np.float64)
+    m.set_params(theta0)
+    xs = [W.make_input(spec, t, 1).astype(np.float64) for t in range(d + 6)]
+    gs = [W.make_grad_out(spec, t, 1).astype(np.float64) for t in range(d + 6)]
+    snapshots = []
+    for t in range(d + 6):
+        snapshots.append(m.get_params())
+        m.forward(xs[t])
+        assert m.queue_state() == (min(t, d) + 1, max(0, t - d), t)
+        if t >= d:                      # warm-up: no gradient has arrived before iteration d
+            s = t - d                   # the batch whose gradient arrives now
+            gin = m.backward_delayed(gs[s])
+            fresh_spec = copy.deepcopy(spec)
+            fresh_spec.delay, fresh_spec.beta = 0, 1.0
+            fresh = OracleModule(fresh_spec, np.float64)
+            fresh.set_params(snapshots[s])
+            fresh.forward(xs[s])
+            gin_fresh = fresh.backward_delayed(gs[s])
+            np.testing.assert_allclose(m.get_grads(), spec.beta * fresh.get_grads(), rtol=1e-12, atol=1e-15)
+            np.testing.assert_allclose(gin, spec.beta * gin_fresh, rtol=1e-12, atol=1e-15)
+            if d > 0 and t > d:
+                assert np.abs(snapshots[s] - m.get_params()).max() > 1e-6   # weights have moved meanwhile
+            before, v_before = m.get_params(), m.get_momentum()
+            m.update(spec.lr)
+            # Eq. 11/12: current weights, delayed gradient
+            gp = m.get_grads() + spec.weight_decay * before
+            v = spec.momentum * v_before + gp
+            np.testing.assert_allclose(m.get_params(), before - spec.lr * v, rtol=1e-12, atol=1e-15)
+
+
+def test_queue_errors():
+    spec = copy.deepcopy(TINY["postact_identity"])
+    spec.delay = 1
+    m = OracleModule(spec)
+    theta, x, g, _ = _inputs(spec)
+    m.set_params(theta)
+    with pytest.raises(QueueEmpty):
+        m.backward_delayed(g)
+    with pytest.raises(NoGrad):
+        m.update(0.1)
+    m.forward(x)
+    m.forward(x)
+    with pytest.raises(QueueFull):
+        m.forward(x)
+    m.backward_delayed(g)
+    m.update(0.1)
+    with pytest.raises(NoGrad):
+        m.update(0.1)
+    assert m.queue_state() == (1, 1, 1)
+
+
+def test_running_statistics():
+    spec = TINY["postact_identity"]
+    theta, x, _, _ = _inputs(spec)
+    m = OracleModule(spec, np.float64)
+    m.set_params(theta)
+    m.forward(x)
+    c1 = m.k.conv_fwd(x, m.theta["0.conv1.w"], 1, 1)
+    M = c1.shape[0] * c1.shape[2] * c1.shape[3]
+    rm, rv = m.running["0.bn1"]
+    np.testing.assert_allclose(rm, 0.1 * c1.mean(axis=(0, 2, 3)), rtol=1e-12)
+    np.testing.assert_allclose(rv, 0.9 + 0.1 * c1.var(axis=(0, 2, 3)) * M / (M - 1), rtol=1e-12)
+    assert m.get_bn_running().size == 2 * 2 * 4
