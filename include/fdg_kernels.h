@@ -1,0 +1,73 @@
+/*
+ * fdg_kernels.h -- C ABI of the individual gfx950 kernels behind the FDG module worker (fdg.h).
+ *
+ * These are the layer operations a module's forward (Section III-A of arXiv 1906.09108) and its
+ * chain-rule backward (Eq. 8, Eq. 9, Eq. 10) are made of, exposed one by one so that each can be
+ * checked against its definition and timed against its roofline.  The paper names the layers only by
+ * architecture (ResNet / WRN, Table III, optimiser in Section V-A); the arithmetic of each entry point
+ * is stated in its comment.
+ *
+ * All pointers are DEVICE pointers.  Activations are NHWC; "bf16" buffers hold raw bfloat16 (uint16_t
+ * storage), "f32" buffers hold float.  Channel counts of bf16 activations must be multiples of 8.
+ * Nothing is allocated; the caller owns every buffer.  `hip_stream` is a hipStream_t (NULL = null
+ * stream); calls only enqueue.  Return value: 0 on success, otherwise the hipError_t of the failed
+ * check or launch (1 = invalid value for a shape the kernels do not take).
+ */
+#ifndef FDG_KERNELS_H_
+#define FDG_KERNELS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Convolution geometry shared by the three passes: ksize 3 (padding 1) or 1 (padding 0), stride 1 or 2,
+ * input [n, h, w, cip] with cip = ci rounded up to 8 (padding channels zero), output
+ * [n, ho, wo, co], ho = (h-1)/stride + 1.  co must be a multiple of 8.                            */
+
+/* y = conv(x, w) (+ addend):  y[n,ho,wo,o] = sum_{r,q,i} x[n, ho*s+r-p, wo*s+q-p, i] * w[o,r,q,i].
+ *   x_b16 [n,h,w,cip]; w_b16 [co][ksize*ksize][cip]; addend_f32 optional [n,ho,wo,co];
+ *   y_f32 / y_b16 optional outputs (at least one).                                                 */
+int fdgk_conv_fwd(const void* x_b16, const void* w_b16, const float* addend_f32, float* y_f32, void* y_b16,
+                  int n, int h, int w, int ci, int co, int ksize, int stride, void* hip_stream);
+
+/* Data gradient, the adjoint of fdgk_conv_fwd in x:
+ *   dx[n,hi,wi,i] = sum_{o,r,q : hi = ho*s+r-p, wi = wo*s+q-p} dy[n,ho,wo,o] * w[o,r,q,i]  (+ addend)
+ *   dy_b16 [n,ho,wo,co]; wt_b16 = the same weights stored [cip][ksize*ksize][co];
+ *   addend_f32 optional [n,h,w,cip]; if addmask_b16 ([n,h,w,cip]) is given the addend counts only
+ *   where addmask > 0 (a ReLU gate);  dx_f32 / dx_b16 optional outputs [n,h,w,cip].               */
+int fdgk_conv_dgrad(const void* dy_b16, const void* wt_b16, const float* addend_f32, const void* addmask_b16,
+                    float* dx_f32, void* dx_b16, int n, int h, int w, int ci, int co, int ksize, int stride,
+                    void* hip_stream);
+
+/* Weight gradient, the adjoint in w, ACCUMULATED into dw_f32 [co][ksize*ksize][ci] with fp32 atomics
+ * (zero it first):  dw[o,r,q,i] += sum_{n,ho,wo} dy[n,ho,wo,o] * x[n, ho*s+r-p, wo*s+q-p, i].       */
+int fdgk_conv_wgrad(const void* x_b16, const void* dy_b16, float* dw_f32, int n, int h, int w, int ci, int co,
+                    int ksize, int stride, void* hip_stream);
+
+/* Training-mode batch normalisation over the m rows of x_b16 [m, c].
+ * stats:  sums_f32[0..c) += sum x, sums_f32[c..2c) += sum x^2   (zero it first).
+ * apply:  y = relu?( gamma*(x-mean)/sqrt(var+eps) + beta  [+ res_f32] ), mean/var (biased) from sums. */
+int fdgk_bn_stats(const void* x_b16, float* sums_f32, int m, int c, void* hip_stream);
+int fdgk_bn_apply(const void* x_b16, const float* sums_f32, const float* gamma, const float* beta,
+                  const float* res_f32, float* y_f32, void* y_b16, int m, int c, float eps, int relu,
+                  void* hip_stream);
+
+/* Backward of y = relu(bn(x) [+ ...]) given dy (fp32 if dy_is_f32 else bf16) and the ReLU output
+ * mask_b16 (gradient passes where mask > 0):  g = dy*[mask>0];  dbeta = sum g;  dgamma = sum g*xhat;
+ *   dx = gamma/sqrt(var+eps) * (g - dbeta/m - xhat*dgamma/m)  (+ addend_f32).
+ * scratch_f32 [2c] must be zero on entry.  dx_f32 / dx_b16 optional.                               */
+int fdgk_bn_bwd(const void* dy, int dy_is_f32, const void* mask_b16, const void* x_b16, const float* sums_f32,
+                const float* gamma, float* scratch_f32, const float* addend_f32, float* dx_f32, void* dx_b16,
+                float* dgamma, float* dbeta, int m, int c, float eps, void* hip_stream);
+
+/* Momentum SGD with coupled weight decay (Eq. 11 with the optimiser of Section V-A), count % 4 == 0:
+ *   g' = g + wd*theta;  v = mu*v + g';  theta = theta - lr*v.                                       */
+int fdgk_sgd(float* theta, float* v, const float* g, size_t count, float lr, float mu, float wd, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FDG_KERNELS_H_ */

@@ -1,0 +1,227 @@
+"""Argument marshalling between Python and libfdg.so.  No arithmetic happens here: torch only owns
+device memory and streams; every step of the module's forward, delayed backward and update runs in
+the library's kernels.  Function names and argument order follow include/fdg.h."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfdg.so")
+
+STATUS_NAMES = {0: "FDG_OK", 1: "FDG_ERR_INVALID_ARG", 2: "FDG_ERR_UNSUPPORTED", 3: "FDG_ERR_WORKSPACE_TOO_SMALL",
+                4: "FDG_ERR_QUEUE_FULL", 5: "FDG_ERR_QUEUE_EMPTY", 6: "FDG_ERR_NO_GRAD", 7: "FDG_ERR_HIP"}
+FDG_OK, FDG_ERR_INVALID_ARG, FDG_ERR_UNSUPPORTED, FDG_ERR_WORKSPACE_TOO_SMALL = 0, 1, 2, 3
+FDG_ERR_QUEUE_FULL, FDG_ERR_QUEUE_EMPTY, FDG_ERR_NO_GRAD, FDG_ERR_HIP = 4, 5, 6, 7
+
+
+class FdgError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {STATUS_NAMES.get(status, status)}")
+
+
+class fdg_layer_desc(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("c_in", ctypes.c_int32), ("c_out", ctypes.c_int32), ("stride", ctypes.c_int32)]
+
+
+class fdg_module_desc(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_int32), ("c_in", ctypes.c_int32), ("h_in", ctypes.c_int32), ("w_in", ctypes.c_int32),
+                ("num_layers", ctypes.c_int32), ("layers", ctypes.POINTER(fdg_layer_desc)),
+                ("delay", ctypes.c_int32), ("is_bottom", ctypes.c_int32), ("num_classes", ctypes.c_int32),
+                ("beta", ctypes.c_float), ("momentum", ctypes.c_float), ("weight_decay", ctypes.c_float),
+                ("bn_eps", ctypes.c_float), ("bn_momentum", ctypes.c_float)]
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+EXPORTS = ["fdg_module_workspace_bytes", "fdg_module_create", "fdg_forward", "fdg_backward_delayed", "fdg_update",
+           "fdg_destroy", "fdg_param_count", "fdg_set_params", "fdg_get_params", "fdg_get_grads", "fdg_get_momentum",
+           "fdg_bn_stat_count", "fdg_get_bn_running", "fdg_output_shape", "fdg_queue_state", "fdg_status_string"]
+
+
+def load() -> ctypes.CDLL:
+    """Load libfdg.so.  There is no fallback: a missing library is an error."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} is not built; run `python -m paper_1906_09108_amd.build` "
+                                "(or __graft_entry__.build()) first")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+    dp = ctypes.POINTER(fdg_module_desc)
+    lib.fdg_module_workspace_bytes.argtypes, lib.fdg_module_workspace_bytes.restype = [dp], sz
+    lib.fdg_module_create.argtypes, lib.fdg_module_create.restype = [dp, vp, sz, vp, ctypes.POINTER(vp)], i32
+    lib.fdg_forward.argtypes, lib.fdg_forward.restype = [vp, vp, vp, vp, vp], i32
+    lib.fdg_backward_delayed.argtypes, lib.fdg_backward_delayed.restype = [vp, vp, vp, vp], i32
+    lib.fdg_update.argtypes, lib.fdg_update.restype = [vp, f32, vp], i32
+    lib.fdg_destroy.argtypes, lib.fdg_destroy.restype = [vp], None
+    lib.fdg_param_count.argtypes, lib.fdg_param_count.restype = [vp], sz
+    for name in ("fdg_set_params", "fdg_get_params", "fdg_get_grads", "fdg_get_momentum", "fdg_get_bn_running"):
+        getattr(lib, name).argtypes, getattr(lib, name).restype = [vp, vp, sz], i32
+    lib.fdg_bn_stat_count.argtypes, lib.fdg_bn_stat_count.restype = [vp], sz
+    lib.fdg_output_shape.argtypes, lib.fdg_output_shape.restype = [vp, ctypes.POINTER(i32 * 4)], i32
+    lib.fdg_queue_state.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]
+    lib.fdg_queue_state.restype = i32
+    lib.fdg_status_string.argtypes, lib.fdg_status_string.restype = [i32], ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def make_desc(spec) -> Tuple[fdg_module_desc, object]:
+    """C descriptor from any object with the descriptor's fields (e.g. fdg_workloads.ModuleSpec).
+    Returns (desc, keepalive)."""
+    arr = (fdg_layer_desc * len(spec.layers))()
+    for i, L in enumerate(spec.layers):
+        arr[i] = fdg_layer_desc(int(L.kind), int(L.c_in), int(L.c_out), int(L.stride))
+    d = fdg_module_desc(int(spec.n), int(spec.c_in), int(spec.h_in), int(spec.w_in), len(spec.layers),
+                        ctypes.cast(arr, ctypes.POINTER(fdg_layer_desc)), int(spec.delay), int(bool(spec.is_bottom)),
+                        int(spec.num_classes), float(spec.beta), float(spec.momentum), float(spec.weight_decay),
+                        float(spec.bn_eps), float(spec.bn_momentum))
+    return d, arr
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _stream_handle(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    h = int(stream.cuda_stream)
+    return h if h else None
+
+
+# ---- the C entry points, same names, torch tensors in place of raw pointers ---------------------
+def fdg_module_workspace_bytes(spec) -> int:
+    d, keep = make_desc(spec)
+    return int(load().fdg_module_workspace_bytes(ctypes.byref(d)))
+
+
+def fdg_module_create(spec, workspace, stream=None) -> int:
+    """workspace: a torch uint8 CUDA tensor of at least fdg_module_workspace_bytes(spec) bytes,
+    256-byte aligned.  Returns the opaque module handle."""
+    d, keep = make_desc(spec)
+    out = ctypes.c_void_p()
+    st = load().fdg_module_create(ctypes.byref(d), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                  _stream_handle(stream), ctypes.byref(out))
+    if st != FDG_OK:
+        raise FdgError(st, "fdg_module_create")
+    return out.value
+
+
+def fdg_forward(handle: int, x, labels, y, stream=None) -> int:
+    return int(load().fdg_forward(handle, _ptr(x), _ptr(labels), _ptr(y), _stream_handle(stream)))
+
+
+def fdg_backward_delayed(handle: int, grad_out, grad_in, stream=None) -> int:
+    return int(load().fdg_backward_delayed(handle, _ptr(grad_out), _ptr(grad_in), _stream_handle(stream)))
+
+
+def fdg_update(handle: int, lr: float, stream=None) -> int:
+    return int(load().fdg_update(handle, float(lr), _stream_handle(stream)))
+
+
+def fdg_destroy(handle: Optional[int]) -> None:
+    if handle:
+        load().fdg_destroy(handle)
+
+
+class FdgModule:
+    """Owns the workspace tensor and the handle of one module; every method is one C call."""
+
+    def __init__(self, spec, device="cuda:0", stream=None):
+        import torch
+        self.torch = torch
+        self.spec = spec
+        self.device = torch.device(device)
+        nbytes = fdg_module_workspace_bytes(spec)
+        if nbytes == 0:
+            raise FdgError(FDG_ERR_UNSUPPORTED, "fdg_module_workspace_bytes")
+        self.workspace_bytes = nbytes
+        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+        off = (-self.workspace.data_ptr()) % 256
+        self._ws_view = self.workspace[off:off + nbytes]
+        self.handle = fdg_module_create(spec, self._ws_view, stream)
+        shp = (ctypes.c_int32 * 4)()
+        load().fdg_output_shape(self.handle, ctypes.byref(shp))
+        self.out_shape = tuple(int(v) for v in shp)
+        self.is_top = bool(spec.layers) and int(spec.layers[-1].kind) in (3, 4)
+
+    def close(self):
+        if getattr(self, "handle", None):
+            self.torch.cuda.synchronize(self.device)
+            fdg_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- hot path ----------------------------------------------------------------------------------
+    def new_output(self):
+        t = self.torch
+        if self.is_top:
+            return t.empty(self.out_shape[3], dtype=t.float32, device=self.device)
+        return t.empty(self.out_shape, dtype=t.float32, device=self.device)
+
+    def forward(self, x, labels=None, y=None, stream=None, check=True):
+        if y is None:
+            y = self.new_output()
+        st = fdg_forward(self.handle, x, labels, y, stream)
+        if check and st != FDG_OK:
+            raise FdgError(st, "fdg_forward")
+        return y if check else (st, y)
+
+    def backward_delayed(self, grad_out=None, grad_in=None, stream=None, check=True):
+        st = fdg_backward_delayed(self.handle, grad_out, grad_in, stream)
+        if check and st != FDG_OK:
+            raise FdgError(st, "fdg_backward_delayed")
+        return grad_in if check else st
+
+    def update(self, lr, stream=None, check=True):
+        st = fdg_update(self.handle, lr, stream)
+        if check and st != FDG_OK:
+            raise FdgError(st, "fdg_update")
+        return st
+
+    # -- host accessors ----------------------------------------------------------------------------
+    def param_count(self) -> int:
+        return int(load().fdg_param_count(self.handle))
+
+    def set_params(self, flat: np.ndarray) -> None:
+        a = np.ascontiguousarray(flat, np.float32)
+        st = load().fdg_set_params(self.handle, a.ctypes.data, a.size)
+        if st != FDG_OK:
+            raise FdgError(st, "fdg_set_params")
+
+    def _get(self, name: str, count: int) -> np.ndarray:
+        a = np.empty(count, np.float32)
+        st = getattr(load(), name)(self.handle, a.ctypes.data, a.size)
+        if st != FDG_OK:
+            raise FdgError(st, name)
+        return a
+
+    def get_params(self):
+        return self._get("fdg_get_params", self.param_count())
+
+    def get_grads(self):
+        return self._get("fdg_get_grads", self.param_count())
+
+    def get_momentum(self):
+        return self._get("fdg_get_momentum", self.param_count())
+
+    def get_bn_running(self):
+        return self._get("fdg_get_bn_running", int(load().fdg_bn_stat_count(self.handle)))
+
+    def queue_state(self) -> Tuple[int, int, int]:
+        o, a, b = ctypes.c_int32(), ctypes.c_int64(), ctypes.c_int64()
+        load().fdg_queue_state(self.handle, ctypes.byref(o), ctypes.byref(a), ctypes.byref(b))
+        return int(o.value), int(a.value), int(b.value)

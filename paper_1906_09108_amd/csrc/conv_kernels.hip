@@ -1,0 +1,459 @@
+// Implicit-GEMM convolutions on gfx950 matrix cores (v_mfma_f32_16x16x32_bf16, fp32 accumulate).
+//
+// Two kernels serve every convolution of an FDG module step (Section III-A of arXiv 1906.09108: the
+// forward of the newest batch, and the chain-rule backward of Eq. 10 on the stale batch):
+//   conv_gather_kernel : out[pixel, c] = sum_{tap,k} in[pixel+tap, k] * w[c, tap, k]
+//                        forward convolution and data gradient (flipped taps, transposed weights,
+//                        stride-2 data gradient as four parity classes).
+//   conv_wgrad_kernel  : dw[co, tap, ci] += sum_pixel dy[pixel, co] * x[pixel+tap, ci]
+//                        the contraction runs over pixels, so both operands are transposed in
+//                        registers on their way to LDS; split over pixels with fp32 atomics.
+//
+// MFMA operand layout used throughout (16x16x32, 64 lanes): lane l supplies row (l & 15) of A and
+// column (l & 15) of B, each with the 8 consecutive k values 8*(l >> 4) .. +7; lane l receives
+// D[4*(l >> 4) + v][l & 15] in accumulator component v.
+#include "fdg_internal.h"
+
+namespace fdg {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  bf16_t l = (bf16_t)lo, h = (bf16_t)hi;
+  return (uint32_t)__builtin_bit_cast(uint16_t, l) | ((uint32_t)__builtin_bit_cast(uint16_t, h) << 16);
+}
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __builtin_bit_cast(float, u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __builtin_bit_cast(float, u & 0xffff0000u); }
+
+// ------------------------------------------------------------------------------------------------
+// gather-form convolution
+// ------------------------------------------------------------------------------------------------
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+__global__ __launch_bounds__(256) void conv_gather_kernel(GatherConvArgs a) {
+  static_assert(WAVES_M * WAVES_N == 4, "four waves");
+  constexpr int PITCH = 40;  // 32 k values + 8 pad: 80-byte rows keep 16-lane b128 reads conflict free
+  constexpr int TM = BM / WAVES_M, TN = BN / WAVES_N;
+  constexpr int FM = TM / 16, FN = TN / 16;
+  constexpr int UX = (BM * 4 + 255) / 256;  // 16-byte units per thread of the pixel tile
+  constexpr int UW = (BN * 4 + 255) / 256;  // ... of the weight tile
+  __shared__ __attribute__((aligned(16))) bf16_t sX[2][BM * PITCH];
+  __shared__ __attribute__((aligned(16))) bf16_t sW[2][BN * PITCH];
+  __shared__ int sTap[16];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
+  const int Mtot = a.N * a.OH * a.OW;
+  const int m0 = blockIdx.x * BM, c0 = blockIdx.y * BN;
+  if (tid < 16) sTap[tid] = tid < a.ntaps ? a.tap[tid < 9 ? tid : 0] : 0;
+
+  // per-thread rows of the two tiles: row = tid/4 + 64*j, fixed k-unit kq = tid%4
+  const int kq = tid & 3;
+  int pbase[UX], ih0[UX], iw0[UX];
+#pragma unroll
+  for (int j = 0; j < UX; ++j) {
+    const int row = (tid >> 2) + 64 * j, m = m0 + row;
+    if (row < BM && m < Mtot) {
+      const int ow = m % a.OW, t2 = m / a.OW, oh = t2 % a.OH, n = t2 / a.OH;
+      pbase[j] = n * a.Hi * a.Wi;
+      ih0[j] = oh * a.in_stride;
+      iw0[j] = ow * a.in_stride;
+    } else {
+      pbase[j] = 0;
+      ih0[j] = -(1 << 20);
+      iw0[j] = 0;
+    }
+  }
+  const bf16_t* wrow[UW];
+  bool wok[UW];
+#pragma unroll
+  for (int j = 0; j < UW; ++j) {
+    const int row = (tid >> 2) + 64 * j, c = c0 + row;
+    wok[j] = row < BN && c < a.w_rows;
+    wrow[j] = a.w + (size_t)(wok[j] ? c : 0) * a.Kw;
+  }
+  const int cpt = a.Ci >> 3;  // 16-byte units per tap
+  int tap = kq / cpt, c8 = kq % cpt;
+  const int nchunks = (a.ntaps * cpt + 3) >> 2;
+
+  f32x4 acc[FN][FM];
+#pragma unroll
+  for (int i = 0; i < FN; ++i)
+#pragma unroll
+    for (int j = 0; j < FM; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  uint4 rx[UX], rw[UW];
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+  __syncthreads();  // sTap visible
+
+  auto load_global = [&]() {
+    const bool tv = tap < a.ntaps;
+    const int tp = tv ? sTap[tap] : pack_tap(0, 0, 0);
+    const int dh = (tp & 0xff) - 8, dw = ((tp >> 8) & 0xff) - 8, kofs = tp >> 16;
+#pragma unroll
+    for (int j = 0; j < UX; ++j) {
+      const int ih = ih0[j] + dh, iw = iw0[j] + dw;
+      const bool ok = tv && (unsigned)ih < (unsigned)a.Hi && (unsigned)iw < (unsigned)a.Wi;
+      rx[j] = ok ? *reinterpret_cast<const uint4*>(a.in + ((size_t)(pbase[j] + ih * a.Wi + iw) * a.Ci + c8 * 8))
+                 : zero4;
+    }
+#pragma unroll
+    for (int j = 0; j < UW; ++j)
+      rw[j] = (tv && wok[j]) ? *reinterpret_cast<const uint4*>(wrow[j] + (size_t)kofs * a.Ci + c8 * 8) : zero4;
+    // advance this thread's k-unit by one chunk (4 units)
+    c8 += 4;
+    while (c8 >= cpt) {
+      c8 -= cpt;
+      ++tap;
+    }
+  };
+  auto store_lds = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < UX; ++j) {
+      const int row = (tid >> 2) + 64 * j;
+      if (row < BM) *reinterpret_cast<uint4*>(&sX[buf][row * PITCH + kq * 8]) = rx[j];
+    }
+#pragma unroll
+    for (int j = 0; j < UW; ++j) {
+      const int row = (tid >> 2) + 64 * j;
+      if (row < BN) *reinterpret_cast<uint4*>(&sW[buf][row * PITCH + kq * 8]) = rw[j];
+    }
+  };
+
+  load_global();
+  store_lds(0);
+  __syncthreads();
+  for (int kc = 0; kc < nchunks; ++kc) {
+    const int buf = kc & 1;
+    const bool more = kc + 1 < nchunks;
+    if (more) load_global();
+    bf16x8 fa[FN], fb[FM];
+#pragma unroll
+    for (int f = 0; f < FN; ++f)
+      fa[f] = *reinterpret_cast<const bf16x8*>(&sW[buf][(wave_n * TN + f * 16 + (lane & 15)) * PITCH + (lane >> 4) * 8]);
+#pragma unroll
+    for (int f = 0; f < FM; ++f)
+      fb[f] = *reinterpret_cast<const bf16x8*>(&sX[buf][(wave_m * TM + f * 16 + (lane & 15)) * PITCH + (lane >> 4) * 8]);
+#pragma unroll
+    for (int i = 0; i < FN; ++i)
+#pragma unroll
+      for (int j = 0; j < FM; ++j) acc[i][j] = mfma16(fa[i], fb[j], acc[i][j]);
+    if (more) store_lds(buf ^ 1);
+    __syncthreads();
+  }
+
+  // epilogue: lane holds 4 consecutive channels of one pixel per accumulator
+#pragma unroll
+  for (int j = 0; j < FM; ++j) {
+    const int m = m0 + wave_m * TM + j * 16 + (lane & 15);
+    if (m >= Mtot) continue;
+    const int ow = m % a.OW, t2 = m / a.OW, oh = t2 % a.OH, n = t2 / a.OH;
+    const size_t opix = ((size_t)n * a.OHf + oh * a.out_stride + a.ooh) * a.OWf + ow * a.out_stride + a.oow;
+#pragma unroll
+    for (int i = 0; i < FN; ++i) {
+      const int c = c0 + wave_n * TN + i * 16 + 4 * (lane >> 4);
+      if (c >= a.Co) continue;
+      const size_t o = opix * a.Co + c;
+      f32x4 v = acc[i][j];
+      if (a.addend) {
+        float4 ad = *reinterpret_cast<const float4*>(a.addend + o);
+        if (a.addmask) {
+          const uint2 mk = *reinterpret_cast<const uint2*>(a.addmask + o);
+          if (!(bf16_lo(mk.x) > 0.f)) ad.x = 0.f;
+          if (!(bf16_hi(mk.x) > 0.f)) ad.y = 0.f;
+          if (!(bf16_lo(mk.y) > 0.f)) ad.z = 0.f;
+          if (!(bf16_hi(mk.y) > 0.f)) ad.w = 0.f;
+        }
+        v[0] += ad.x;
+        v[1] += ad.y;
+        v[2] += ad.z;
+        v[3] += ad.w;
+      }
+      if (a.out_f32) *reinterpret_cast<float4*>(a.out_f32 + o) = make_float4(v[0], v[1], v[2], v[3]);
+      if (a.out_b16)
+        *reinterpret_cast<uint2*>(a.out_b16 + o) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+    }
+  }
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+static hipError_t run_gather(const GatherConvArgs& a, hipStream_t s) {
+  const int Mtot = a.N * a.OH * a.OW;
+  dim3 grid((Mtot + BM - 1) / BM, (a.Co + BN - 1) / BN, 1);
+  hipLaunchKernelGGL((conv_gather_kernel<BM, BN, WAVES_M, WAVES_N>), grid, dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_conv_gather(const GatherConvArgs& a, hipStream_t s) {
+  if (a.Ci % 8 != 0 || a.Co % 4 != 0 || a.ntaps < 0 || a.ntaps > 9 || a.N * a.OH * a.OW <= 0 || a.Kw % 8 != 0)
+    return hipErrorInvalidValue;
+  if (a.Co <= 16) return run_gather<256, 16, 4, 1>(a, s);
+  if (a.Co <= 32) return run_gather<256, 32, 4, 1>(a, s);
+  if (a.Co <= 64) return run_gather<128, 64, 2, 2>(a, s);
+  return run_gather<128, 128, 2, 2>(a, s);
+}
+
+// ------------------------------------------------------------------------------------------------
+// weight gradient
+// ------------------------------------------------------------------------------------------------
+// 8 pixels x 8 channels (one uint4 per pixel) -> per channel the 8 pixels as one uint4
+__device__ __forceinline__ void transpose8x8(const uint4 (&r)[8], uint4 (&o)[8]) {
+#define FDG_TR_PAIR(F, P)                                                        \
+  {                                                                              \
+    uint32_t lo[4], hi[4];                                                       \
+    _Pragma("unroll") for (int q = 0; q < 4; ++q) {                              \
+      const uint32_t p0 = r[2 * q].F, p1 = r[2 * q + 1].F;                       \
+      lo[q] = (p0 & 0xffffu) | (p1 << 16);                                       \
+      hi[q] = (p0 >> 16) | (p1 & 0xffff0000u);                                   \
+    }                                                                            \
+    o[2 * P] = make_uint4(lo[0], lo[1], lo[2], lo[3]);                           \
+    o[2 * P + 1] = make_uint4(hi[0], hi[1], hi[2], hi[3]);                       \
+  }
+  FDG_TR_PAIR(x, 0)
+  FDG_TR_PAIR(y, 1)
+  FDG_TR_PAIR(z, 2)
+  FDG_TR_PAIR(w, 3)
+#undef FDG_TR_PAIR
+}
+
+struct WgradLaunch {
+  int chunks_per_split;
+  int ci_tiles;
+};
+
+template <int BM, int BN, int WM, int WN, int WK>
+__global__ __launch_bounds__(256) void conv_wgrad_kernel(WgradArgs a, WgradLaunch L) {
+  static_assert(WM * WN * WK == 4, "four waves");
+  constexpr int KSTEPS = WK == 1 ? 2 : 1;
+  constexpr int BK = 32 * WK * KSTEPS;
+  constexpr int PITCH = BK + 8;
+  constexpr int TM = BM / WM, TN = BN / WN;
+  constexpr int FA = TM / 16, FB = TN / 16;
+  constexpr int CGA = BM / 8, CGB = BN / 8, PG = BK / 8;
+  constexpr int NUA = CGA * PG, NUB = CGB * PG;
+  static_assert(NUA + NUB <= 256, "one 8x8 unit per thread");
+  __shared__ __attribute__((aligned(16))) bf16_t sA[2][BM * PITCH];
+  __shared__ __attribute__((aligned(16))) bf16_t sB[2][BN * PITCH];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave % WM, wn = (wave / WM) % WN, wk = wave / (WM * WN);
+  const int Mtot = a.N * a.OH * a.OW;
+  const int co0 = blockIdx.x * BM;
+  const int tapi = blockIdx.y / L.ci_tiles, ci0 = (blockIdx.y % L.ci_tiles) * BN;
+  const int tp = a.tap[tapi];
+  const int dh = (tp & 0xff) - 8, dw = ((tp >> 8) & 0xff) - 8;
+  const int total_chunks = (Mtot + BK - 1) / BK;
+  const int chunk_lo = blockIdx.z * L.chunks_per_split;
+  const int chunk_hi = min(total_chunks, chunk_lo + L.chunks_per_split);
+  const bool row8 = (a.OW % 8) == 0;  // the 8 pixels of a unit share one image row
+
+  const bool isA = tid < NUA, isB = !isA && tid < NUA + NUB;
+  const int u = isA ? tid : tid - NUA;
+  const int cg = isA ? u % CGA : u % CGB, pg = isA ? u / CGA : u / CGB;
+  const int chan = (isA ? co0 : ci0) + cg * 8;
+  const bool chan_ok = isA ? chan < a.Co : (isB && chan < a.Cx);
+
+  f32x4 acc[FA][FB];
+#pragma unroll
+  for (int i = 0; i < FA; ++i)
+#pragma unroll
+    for (int j = 0; j < FB; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  uint4 r[8];
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+  auto load_global = [&](int chunk) {
+    const int mb = chunk * BK + pg * 8;
+    if (isA) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int m = mb + i;
+        r[i] = (chan_ok && m < Mtot) ? *reinterpret_cast<const uint4*>(a.dy + (size_t)m * a.Co + chan) : zero4;
+      }
+    } else if (row8) {
+      const int ow0 = mb % a.OW, t2 = mb / a.OW, oh = t2 % a.OH, n = t2 / a.OH;
+      const int ih = oh * a.stride + dh;
+      const bool rowok = chan_ok && mb < Mtot && (unsigned)ih < (unsigned)a.Hi;
+      const size_t rbase = ((size_t)n * a.Hi + ih) * a.Wi;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int iw = (ow0 + i) * a.stride + dw;
+        r[i] = (rowok && (unsigned)iw < (unsigned)a.Wi)
+                   ? *reinterpret_cast<const uint4*>(a.x + (rbase + iw) * a.Cx + chan)
+                   : zero4;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int m = mb + i;
+        const int ow = m % a.OW, t2 = m / a.OW, oh = t2 % a.OH, n = t2 / a.OH;
+        const int ih = oh * a.stride + dh, iw = ow * a.stride + dw;
+        const bool ok = chan_ok && m < Mtot && (unsigned)ih < (unsigned)a.Hi && (unsigned)iw < (unsigned)a.Wi;
+        r[i] = ok ? *reinterpret_cast<const uint4*>(a.x + (((size_t)n * a.Hi + ih) * a.Wi + iw) * a.Cx + chan) : zero4;
+      }
+    }
+  };
+  auto store_lds = [&](int buf) {
+    if (!(isA || isB)) return;
+    uint4 o[8];
+    transpose8x8(r, o);
+    bf16_t* base = (isA ? sA[buf] : sB[buf]) + (cg * 8) * PITCH + pg * 8;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) *reinterpret_cast<uint4*>(base + c * PITCH) = o[c];
+  };
+
+  if (chunk_lo < chunk_hi) {
+    load_global(chunk_lo);
+    store_lds(0);
+  }
+  __syncthreads();
+  for (int ch = chunk_lo; ch < chunk_hi; ++ch) {
+    const int buf = (ch - chunk_lo) & 1;
+    const bool more = ch + 1 < chunk_hi;
+    if (more) load_global(ch + 1);
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      const int kslot = (WK == 1 ? ks : wk) * 32 + (lane >> 4) * 8;
+      bf16x8 fa[FA], fb[FB];
+#pragma unroll
+      for (int f = 0; f < FA; ++f)
+        fa[f] = *reinterpret_cast<const bf16x8*>(&sA[buf][(wm * TM + f * 16 + (lane & 15)) * PITCH + kslot]);
+#pragma unroll
+      for (int f = 0; f < FB; ++f)
+        fb[f] = *reinterpret_cast<const bf16x8*>(&sB[buf][(wn * TN + f * 16 + (lane & 15)) * PITCH + kslot]);
+#pragma unroll
+      for (int i = 0; i < FA; ++i)
+#pragma unroll
+        for (int j = 0; j < FB; ++j) acc[i][j] = mfma16(fa[i], fb[j], acc[i][j]);
+    }
+    if (more) store_lds(buf ^ 1);
+    __syncthreads();
+  }
+
+  // D[co][ci]: lane holds co = 4*(lane>>4)+v, ci = lane&15
+  if (chunk_lo >= chunk_hi) return;
+#pragma unroll
+  for (int i = 0; i < FA; ++i)
+#pragma unroll
+    for (int j = 0; j < FB; ++j) {
+      const int ci = ci0 + wn * TN + j * 16 + (lane & 15);
+      if (ci >= a.Ci) continue;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int co = co0 + wm * TM + i * 16 + 4 * (lane >> 4) + v;
+        if (co < a.Co) atomicAdd(a.dw + ((size_t)co * a.ntaps + tapi) * a.Ci + ci, acc[i][j][v]);
+      }
+    }
+}
+
+template <int BM, int BN, int WM, int WN, int WK>
+static hipError_t run_wgrad(const WgradArgs& a, hipStream_t s) {
+  constexpr int BK = 32 * WK * (WK == 1 ? 2 : 1);
+  const int Mtot = a.N * a.OH * a.OW;
+  const int co_tiles = (a.Co + BM - 1) / BM, ci_tiles = (a.Ci + BN - 1) / BN;
+  const int total_chunks = (Mtot + BK - 1) / BK;
+  const int base = co_tiles * ci_tiles * a.ntaps;
+  int splits = (1024 + base - 1) / base;
+  if (splits > total_chunks) splits = total_chunks;
+  if (splits < 1) splits = 1;
+  WgradLaunch L;
+  L.chunks_per_split = (total_chunks + splits - 1) / splits;
+  L.ci_tiles = ci_tiles;
+  splits = (total_chunks + L.chunks_per_split - 1) / L.chunks_per_split;
+  dim3 grid(co_tiles, ci_tiles * a.ntaps, splits);
+  hipLaunchKernelGGL((conv_wgrad_kernel<BM, BN, WM, WN, WK>), grid, dim3(256), 0, s, a, L);
+  return hipGetLastError();
+}
+
+hipError_t launch_conv_wgrad(const WgradArgs& a, hipStream_t s) {
+  if (a.Co % 8 != 0 || a.Cx % 8 != 0 || a.Ci > a.Cx || a.ntaps < 1 || a.ntaps > 9 || a.N * a.OH * a.OW <= 0)
+    return hipErrorInvalidValue;
+  if (a.Co <= 64 && a.Cx <= 64) return run_wgrad<32, 32, 1, 1, 4>(a, s);
+  return run_wgrad<128, 128, 2, 2, 1>(a, s);
+}
+
+// ------------------------------------------------------------------------------------------------
+// geometry of the three passes of one convolution
+// ------------------------------------------------------------------------------------------------
+hipError_t conv_forward(const ConvShape& c, const bf16_t* x, const bf16_t* w, const float* addend, float* out_f32,
+                        bf16_t* out_b16, hipStream_t s) {
+  GatherConvArgs a{};
+  a.in = x; a.w = w; a.addend = addend; a.addmask = nullptr; a.out_f32 = out_f32; a.out_b16 = out_b16;
+  a.N = c.N; a.Hi = c.Hi; a.Wi = c.Wi; a.Ci = c.Cip;
+  a.OH = c.Ho(); a.OW = c.Wo(); a.in_stride = c.stride;
+  a.OHf = c.Ho(); a.OWf = c.Wo(); a.out_stride = 1; a.ooh = 0; a.oow = 0;
+  a.Co = c.Co; a.w_rows = c.Co; a.Kw = c.T * c.Cip;
+  a.ntaps = c.T;
+  if (c.T == 9) {
+    for (int r = 0; r < 3; ++r)
+      for (int q = 0; q < 3; ++q) a.tap[r * 3 + q] = pack_tap(r - 1, q - 1, r * 3 + q);
+  } else {
+    a.tap[0] = pack_tap(0, 0, 0);
+  }
+  return launch_conv_gather(a, s);
+}
+
+hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
+                      const bf16_t* addmask, float* out_f32, bf16_t* out_b16, hipStream_t s) {
+  GatherConvArgs a{};
+  a.in = dy; a.w = wt; a.addend = addend; a.addmask = addmask; a.out_f32 = out_f32; a.out_b16 = out_b16;
+  a.N = c.N; a.Hi = c.Ho(); a.Wi = c.Wo(); a.Ci = c.Co;
+  a.in_stride = 1;
+  a.OHf = c.Hi; a.OWf = c.Wi;
+  a.Co = c.Cip; a.w_rows = c.Cip; a.Kw = c.T * c.Co;
+  if (c.stride == 1) {
+    // input pixel (hi, wi) receives dy[hi + 1 - r, wi + 1 - q] * w[., r, q, .]
+    a.OH = c.Hi; a.OW = c.Wi; a.out_stride = 1; a.ooh = 0; a.oow = 0;
+    a.ntaps = c.T;
+    if (c.T == 9) {
+      for (int r = 0; r < 3; ++r)
+        for (int q = 0; q < 3; ++q) a.tap[r * 3 + q] = pack_tap(1 - r, 1 - q, r * 3 + q);
+    } else {
+      a.tap[0] = pack_tap(0, 0, 0);
+    }
+    return launch_conv_gather(a, s);
+  }
+  // stride 2: input pixels of one parity class (ph, pw) share one set of taps:
+  // hi = 2*oh + ph receives tap r only if hi + 1 - r is even, from output row (hi + 1 - r) / 2.
+  for (int ph = 0; ph < 2; ++ph)
+    for (int pw = 0; pw < 2; ++pw) {
+      a.OH = (c.Hi - ph + 1) / 2; a.OW = (c.Wi - pw + 1) / 2;
+      if (a.OH <= 0 || a.OW <= 0) continue;
+      a.out_stride = 2; a.ooh = ph; a.oow = pw;
+      a.ntaps = 0;
+      if (c.T == 9) {
+        for (int r = 0; r < 3; ++r) {
+          if (((ph + 1 - r) & 1) != 0) continue;
+          for (int q = 0; q < 3; ++q) {
+            if (((pw + 1 - q) & 1) != 0) continue;
+            a.tap[a.ntaps++] = pack_tap((ph + 1 - r) / 2, (pw + 1 - q) / 2, r * 3 + q);
+          }
+        }
+      } else if (ph == 0 && pw == 0) {
+        a.tap[a.ntaps++] = pack_tap(0, 0, 0);
+      }
+      hipError_t e = launch_conv_gather(a, s);
+      if (e != hipSuccess) return e;
+    }
+  return hipSuccess;
+}
+
+hipError_t conv_wgrad(const ConvShape& c, const bf16_t* x, const bf16_t* dy, float* dw, hipStream_t s) {
+  WgradArgs a{};
+  a.dy = dy; a.x = x; a.dw = dw;
+  a.N = c.N; a.OH = c.Ho(); a.OW = c.Wo(); a.Co = c.Co;
+  a.Hi = c.Hi; a.Wi = c.Wi; a.Cx = c.Cip; a.Ci = c.Ci;
+  a.stride = c.stride; a.ntaps = c.T;
+  if (c.T == 9) {
+    for (int r = 0; r < 3; ++r)
+      for (int q = 0; q < 3; ++q) a.tap[r * 3 + q] = pack_tap(r - 1, q - 1, 0);
+  } else {
+    a.tap[0] = pack_tap(0, 0, 0);
+  }
+  return launch_conv_wgrad(a, s);
+}
+
+}  // namespace fdg

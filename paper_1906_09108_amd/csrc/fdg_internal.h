@@ -1,0 +1,149 @@
+// Internal launch interface between the host-side module object and the gfx950 kernels.
+// Everything here works on device pointers; activations are NHWC, bf16 for MFMA operands and
+// fp32 for the residual stream.  Nothing in this header is part of the C ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace fdg {
+
+typedef __bf16 bf16_t;
+
+// One filter tap of a gather-form convolution: input pixel = (oh*in_stride + dh, ow*in_stride + dw),
+// weight k-offset = kofs * Ci.  Packed as (dh+8) | (dw+8) << 8 | kofs << 16.
+__host__ __device__ static inline int pack_tap(int dh, int dw, int kofs) { return (dh + 8) | ((dw + 8) << 8) | (kofs << 16); }
+
+// out[pix(m), c] = sum_{tap, k} in[pixel(m, tap), k] * w[c, kofs(tap)*Ci + k]  (+ addend)
+// Rows m enumerate an output grid [N, OH, OW]; the output pixel of row (n, oh, ow) is
+// (n, oh*out_stride + ooh, ow*out_stride + oow) in a tensor [N, OHf, OWf, Co].  Forward convolution,
+// stride-1 data gradient and each parity class of a stride-2 data gradient are all of this form.
+struct GatherConvArgs {
+  const bf16_t* in;      // [N, Hi, Wi, Ci] bf16, Ci % 8 == 0
+  const bf16_t* w;       // [w_rows, Kw] bf16, k contiguous
+  const float* addend;   // optional fp32 tensor indexed like the output
+  const bf16_t* addmask; // optional: addend counts only where this bf16 tensor (output indexing) is > 0
+  float* out_f32;        // optional fp32 output
+  bf16_t* out_b16;       // optional bf16 output
+  int N, Hi, Wi, Ci;
+  int OH, OW, in_stride;
+  int OHf, OWf, out_stride, ooh, oow;
+  int Co;                // output channel pitch, % 4 == 0
+  int w_rows;            // weight rows that exist (<= Co); the other output channels are zero
+  int Kw;                // weight row pitch in elements
+  int ntaps;
+  int tap[9];
+};
+hipError_t launch_conv_gather(const GatherConvArgs& a, hipStream_t s);
+
+// dw[co, tap, ci] += sum_m dy[m, co] * x[pixel(m, tap), ci]   (fp32 atomics; dw must be pre-zeroed)
+struct WgradArgs {
+  const bf16_t* dy;  // [N, OH, OW, Co] bf16, Co % 8 == 0
+  const bf16_t* x;   // [N, Hi, Wi, Cx] bf16, Cx % 8 == 0
+  float* dw;         // [Co, ntaps, Ci] fp32
+  int N, OH, OW, Co;
+  int Hi, Wi, Cx, Ci; // Ci = real input channels (<= Cx)
+  int stride;
+  int ntaps;
+  int tap[9];        // pack_tap(dh, dw, 0)
+};
+hipError_t launch_conv_wgrad(const WgradArgs& a, hipStream_t s);
+
+// One convolution of a module: 3x3 with padding 1 (T = 9) or 1x1 with padding 0 (T = 1), stride 1 or 2.
+// Activations carry Cip = Ci rounded up to 8 channels (the padding channels hold zeros).
+struct ConvShape {
+  int N, Hi, Wi, Ci, Cip, Co, T, stride;
+  int Ho() const { return (Hi - 1) / stride + 1; }
+  int Wo() const { return (Wi - 1) / stride + 1; }
+};
+// y[N,Ho,Wo,Co] = conv(x[N,Hi,Wi,Cip], w[Co][T][Cip]) (+ addend)
+hipError_t conv_forward(const ConvShape& c, const bf16_t* x, const bf16_t* w, const float* addend, float* out_f32,
+                        bf16_t* out_b16, hipStream_t s);
+// dx[N,Hi,Wi,Cip] = conv^T(dy[N,Ho,Wo,Co], wt[Cip][T][Co]) (+ addend, optionally only where addmask > 0)
+hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
+                      const bf16_t* addmask, float* out_f32, bf16_t* out_b16, hipStream_t s);
+// dw[Co][T][Ci] += sum over pixels of dy * x   (fp32 atomics)
+hipError_t conv_wgrad(const ConvShape& c, const bf16_t* x, const bf16_t* dy, float* dw, hipStream_t s);
+
+// Batch-norm pieces on [M, C] NHWC tensors (C % 8 == 0, C <= 2048).
+// sums = [sum_c | sumsq_c] fp32, pre-zeroed; accumulated with atomics.
+hipError_t launch_bn_stats(const bf16_t* x, float* sums, int M, int C, hipStream_t s);
+
+struct BnApplyArgs {
+  const bf16_t* x;       // [M, C]
+  const float* sums;     // [2C] of x
+  const float* gamma;    // [C]
+  const float* beta;     // [C]
+  const float* res_f32;  // optional fp32 residual [M, C]
+  const bf16_t* x2;      // optional second normalised operand (projection shortcut) [M, C]
+  const float* sums2;    // its sums, gamma, beta
+  const float* gamma2;
+  const float* beta2;
+  float* out_f32;        // optional
+  bf16_t* out_b16;       // optional
+  float* run_mean;       // optional running statistics of x (updated by block 0)
+  float* run_var;
+  float* run_mean2;      // optional running statistics of x2
+  float* run_var2;
+  int M, C;
+  float eps, momentum;
+  int relu;
+};
+hipError_t launch_bn_apply(const BnApplyArgs& a, hipStream_t s);
+
+// Backward: g = dy * [mask > 0];  bsums = [sum g | sum g*xhat] (pre-zeroed, atomics)
+struct BnBwdArgs {
+  const void* dy;        // [M, C] fp32 or bf16 (dy_is_f32)
+  int dy_is_f32;
+  const bf16_t* mask;    // [M, C] ReLU output (or pre-activation sign carrier); required
+  const bf16_t* x;       // [M, C] the BN input saved by the forward
+  const float* sums;     // forward sums of x
+  const float* gamma;    // snapshot gamma
+  float* bsums;          // [2C]
+  const float* addend;   // optional fp32 [M, C] added to dx (apply only)
+  float* out_f32;        // optional dx
+  bf16_t* out_b16;       // optional dx
+  float* dgamma;         // [C] written by apply
+  float* dbeta;          // [C]
+  int M, C;
+  float eps;
+};
+hipError_t launch_bn_bwd_reduce(const BnBwdArgs& a, hipStream_t s);
+hipError_t launch_bn_bwd_apply(const BnBwdArgs& a, hipStream_t s);
+
+// Layout changes at the module boundary.  scale multiplies every element (beta of Eq. 15).
+hipError_t launch_nchw_to_nhwc(const float* src, float* dst_f32, bf16_t* dst_b16, int N, int C, int HW, int Cp,
+                               float scale, hipStream_t s);
+hipError_t launch_nhwc_to_nchw(const float* src, float* dst, int N, int C, int HW, int Cp, hipStream_t s);
+
+// Head: pooled[n,c] = mean_hw o[n,hw,c];  logits = pooled W^T + b;  softmax cross-entropy.
+hipError_t launch_avgpool(const bf16_t* o, float* pooled, int N, int HW, int C, hipStream_t s);
+hipError_t launch_fc_fwd(const float* pooled, const float* W, const float* b, float* logits, int N, int C, int J,
+                         hipStream_t s);
+// y[0] = mean loss, y[1 + n*J + j] = logits; dl[n,j] = (softmax - onehot)/N
+hipError_t launch_softmax_ce(const float* logits, const int32_t* labels, float* y, float* dl, int N, int J,
+                             hipStream_t s);
+hipError_t launch_fc_bwd(const float* pooled, const float* W, const float* dl, float* dW, float* db, float* dp,
+                         int N, int C, int J, hipStream_t s);
+// g[n,hw,c] = dp[n,c]/HW
+hipError_t launch_pool_bwd(const float* dp, float* g_f32, bf16_t* g_b16, int N, int HW, int C, hipStream_t s);
+
+// theta, v, g flat fp32 (count % 4 == 0):  g' = g + wd*theta;  v = mu*v + g';  theta -= lr*v
+hipError_t launch_sgd(float* theta, float* v, const float* g, size_t count, float lr, float mu, float wd,
+                      hipStream_t s);
+
+// bf16 copies of every convolution weight of the module, one launch.  Entry i describes one conv.
+struct WeightEmitEntry {
+  uint32_t src_off;    // fp32 master [Co][T][Ci], element offset in the parameter arena
+  uint32_t w_off;      // bf16 [Co][T][Cip] element offset in the slot's weight arena (forward / wgrad layout)
+  uint32_t wt_off;     // bf16 [Cip][T][Co] element offset (data-gradient layout)
+  int32_t Co, T, Ci, Cip;
+  uint32_t block_start; // first block of this conv in the launch
+};
+hipError_t launch_emit_weights(const float* params, bf16_t* warena, const WeightEmitEntry* table_dev, int nconv,
+                               int total_blocks, hipStream_t s);
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);  // bytes % 16 == 0
+hipError_t launch_fill_f32(float* p, size_t count, float v, hipStream_t s);
+
+}  // namespace fdg

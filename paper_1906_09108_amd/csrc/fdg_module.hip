@@ -1,0 +1,713 @@
+// Host side of one FDG module worker: descriptor validation, workspace plan, the FIFO ring of saved
+// forwards, and the launch sequences of forward / delayed backward / update (Section III-A, Eq. 10,
+// Eq. 11 and Eq. 15 of arXiv 1906.09108).  This file holds no arithmetic: every number is produced
+// by the kernels in conv_kernels.hip and stream_kernels.hip.
+#include <new>
+#include <vector>
+
+#include "../../include/fdg.h"
+#include "fdg_internal.h"
+
+using namespace fdg;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline int round8(int c) { return (c + 7) / 8 * 8; }
+
+struct ConvInfo {
+  ConvShape sh;
+  size_t p_off;                // fp32 master [Co][T][Ci] in the parameter arena (elements)
+  size_t w_off, wt_off;        // bf16 copies in a slot's weight arena (elements)
+};
+struct BnInfo {
+  int C, M;
+  size_t gamma_off, beta_off;  // parameter arena (elements)
+  size_t stat_off;             // offset of this BN's [2C] block in every per-BN fp32 array
+};
+struct ParamTensor {           // one tensor of the external flat order
+  size_t ext_off, int_off, count;
+  int conv;                    // index into convs, or -1 (stored as is)
+};
+struct LayerPlan {
+  int kind, c_in, c_out, stride;
+  int Hi, Wi, Ho, Wo;
+  bool projects;
+  int conv[3];                 // conv1, conv2, projection (or stem conv in [0])
+  int bn[3];                   // bn1, bn2, bnp (stem / head bn in [0])
+  size_t act[5];               // byte offsets of saved bf16 tensors in a slot (meaning depends on kind)
+  size_t out_b;                // byte offset of this layer's bf16 output in a slot (stream copy)
+  size_t fc_w_off, fc_b_off;   // parameter arena (elements)
+};
+
+struct Plan {
+  fdg_module_desc d;
+  std::vector<fdg_layer_desc> layers;
+  std::vector<LayerPlan> L;
+  std::vector<ConvInfo> convs;
+  std::vector<BnInfo> bns;
+  std::vector<ParamTensor> ptensors;
+  bool is_top = false;
+  int Cp_in = 0;               // channel pitch of the module input copy
+  int out_c = 0, out_h = 0, out_w = 0;
+  size_t ext_params = 0;       // external parameter count
+  size_t conv_elems = 0;       // fp32 conv region (elements)
+  size_t P = 0;                // internal parameter arena (elements, multiple of 4)
+  size_t small_off = 0, small_count = 0;
+  size_t stat_floats = 0;      // 2 * sum of BN channels
+  size_t warena_elems = 0;     // bf16 elements of one slot's weight arena
+  size_t emit_blocks = 0;
+  size_t maxE = 0;             // largest activation tensor in elements
+  int head_C = 0, head_HW = 0;
+  // workspace byte offsets
+  size_t o_params = 0, o_mom = 0, o_grads = 0, o_bsums = 0, o_running = 0, o_table = 0, o_slots = 0, slot_bytes = 0;
+  size_t s_warena = 0, s_small = 0, s_sums = 0, s_xin = 0, s_acts = 0, s_pooled = 0, s_dl = 0, s_logits = 0, s_labels = 0;
+  size_t o_S[2] = {0, 0}, o_G[2] = {0, 0}, o_GB[2] = {0, 0}, o_T[2] = {0, 0}, o_TP = 0, o_dp = 0;
+  size_t total = 0;
+};
+
+bool build_plan(const fdg_module_desc* desc, Plan& p, fdg_status* why) {
+  *why = FDG_ERR_INVALID_ARG;
+  if (!desc || !desc->layers || desc->num_layers <= 0) return false;
+  if (desc->n <= 0 || desc->c_in <= 0 || desc->h_in <= 0 || desc->w_in <= 0 || desc->delay < 0) return false;
+  if (!(desc->beta > 0.f && desc->beta <= 1.f) || !(desc->bn_eps > 0.f)) return false;
+  if (desc->momentum < 0.f || desc->weight_decay < 0.f || desc->bn_momentum < 0.f || desc->bn_momentum > 1.f) return false;
+  p.d = *desc;
+  p.layers.assign(desc->layers, desc->layers + desc->num_layers);
+  p.d.layers = nullptr;
+  const int N = desc->n;
+  int c = desc->c_in, h = desc->h_in, w = desc->w_in;
+  p.Cp_in = round8(c);
+  p.maxE = (size_t)N * h * w * p.Cp_in;
+  size_t act_bytes = 0, ext = 0, small = 0;
+  auto add_conv = [&](int Co, int Ci, int T, int stride, int Hi, int Wi) {
+    ConvInfo ci{};
+    ci.sh = ConvShape{N, Hi, Wi, Ci, round8(Ci), Co, T, stride};
+    ci.p_off = p.conv_elems;
+    p.conv_elems += (size_t)Co * T * Ci;
+    ci.w_off = p.warena_elems;
+    p.warena_elems += align_up((size_t)Co * T * ci.sh.Cip, 128);
+    ci.wt_off = p.warena_elems;
+    p.warena_elems += align_up((size_t)ci.sh.Cip * T * Co, 128);
+    p.convs.push_back(ci);
+    return (int)p.convs.size() - 1;
+  };
+  auto add_bn = [&](int C, int M) {
+    BnInfo b{};
+    b.C = C; b.M = M;
+    b.stat_off = p.stat_floats;
+    p.stat_floats += 2 * (size_t)C;
+    p.bns.push_back(b);
+    return (int)p.bns.size() - 1;
+  };
+  auto save = [&](size_t elems) {  // bf16 tensor saved in the slot
+    const size_t off = act_bytes;
+    act_bytes += align_up(elems * 2, kAlign);
+    if (elems > p.maxE) p.maxE = elems;
+    return off;
+  };
+  // external tensors are appended in the documented order; small tensors get their internal offset later
+  struct Pending { int kind; int conv; int bn; int which; size_t count; };  // which: 0 gamma, 1 beta, 2 fc_w, 3 fc_b
+  std::vector<Pending> pend;
+  for (int i = 0; i < desc->num_layers; ++i) {
+    const fdg_layer_desc& ld = p.layers[i];
+    LayerPlan lp{};
+    lp.kind = ld.kind; lp.c_in = ld.c_in; lp.c_out = ld.c_out; lp.stride = ld.stride;
+    lp.conv[0] = lp.conv[1] = lp.conv[2] = -1;
+    lp.bn[0] = lp.bn[1] = lp.bn[2] = -1;
+    if (ld.c_in != c) return false;
+    const bool head = ld.kind == FDG_HEAD_POSTACT || ld.kind == FDG_HEAD_PREACT;
+    if (head) {
+      if (i != desc->num_layers - 1 || desc->num_classes <= 0 || desc->num_classes > 1024) return false;
+      if (c % 8 != 0 || c > 2048) { *why = FDG_ERR_UNSUPPORTED; return false; }
+      lp.Hi = lp.Ho = h; lp.Wi = lp.Wo = w;
+      p.is_top = true;
+      p.head_C = c; p.head_HW = h * w;
+      if (ld.kind == FDG_HEAD_PREACT) {
+        lp.bn[0] = add_bn(c, N * h * w);
+        pend.push_back({0, -1, lp.bn[0], 0, (size_t)c});
+        pend.push_back({0, -1, lp.bn[0], 1, (size_t)c});
+        lp.act[0] = save((size_t)N * h * w * c);  // o = relu(bn(x))
+      }
+      pend.push_back({0, -1, i, 2, (size_t)desc->num_classes * c});
+      pend.push_back({0, -1, i, 3, (size_t)desc->num_classes});
+      p.L.push_back(lp);
+      break;
+    }
+    if (ld.kind != FDG_STEM_CONV_BN_RELU && ld.kind != FDG_BASIC_POSTACT && ld.kind != FDG_BASIC_PREACT) return false;
+    if (ld.c_out <= 0 || (ld.stride != 1 && ld.stride != 2)) return false;
+    if (ld.c_out % 8 != 0 || ld.c_out > 2048) { *why = FDG_ERR_UNSUPPORTED; return false; }
+    if (ld.kind != FDG_STEM_CONV_BN_RELU && (c % 8 != 0 || c > 2048)) { *why = FDG_ERR_UNSUPPORTED; return false; }
+    const int ho = (h - 1) / ld.stride + 1, wo = (w - 1) / ld.stride + 1;
+    lp.Hi = h; lp.Wi = w; lp.Ho = ho; lp.Wo = wo;
+    lp.projects = ld.kind != FDG_STEM_CONV_BN_RELU && (ld.stride != 1 || ld.c_in != ld.c_out);
+    const size_t Ein = (size_t)N * h * w * round8(c), Eout = (size_t)N * ho * wo * ld.c_out;
+    if (ld.kind == FDG_STEM_CONV_BN_RELU) {
+      lp.conv[0] = add_conv(ld.c_out, c, 9, ld.stride, h, w);
+      lp.bn[0] = add_bn(ld.c_out, N * ho * wo);
+      pend.push_back({1, lp.conv[0], -1, 0, 0});
+      pend.push_back({0, -1, lp.bn[0], 0, (size_t)ld.c_out});
+      pend.push_back({0, -1, lp.bn[0], 1, (size_t)ld.c_out});
+      lp.act[0] = save(Eout);  // c0
+    } else if (ld.kind == FDG_BASIC_POSTACT) {
+      lp.conv[0] = add_conv(ld.c_out, c, 9, ld.stride, h, w);
+      lp.bn[0] = add_bn(ld.c_out, N * ho * wo);
+      lp.conv[1] = add_conv(ld.c_out, ld.c_out, 9, 1, ho, wo);
+      lp.bn[1] = add_bn(ld.c_out, N * ho * wo);
+      pend.push_back({1, lp.conv[0], -1, 0, 0});
+      pend.push_back({0, -1, lp.bn[0], 0, (size_t)ld.c_out});
+      pend.push_back({0, -1, lp.bn[0], 1, (size_t)ld.c_out});
+      pend.push_back({1, lp.conv[1], -1, 0, 0});
+      pend.push_back({0, -1, lp.bn[1], 0, (size_t)ld.c_out});
+      pend.push_back({0, -1, lp.bn[1], 1, (size_t)ld.c_out});
+      lp.act[0] = save(Eout);  // c1
+      lp.act[1] = save(Eout);  // a1
+      lp.act[2] = save(Eout);  // c2
+      if (lp.projects) {
+        lp.conv[2] = add_conv(ld.c_out, c, 1, ld.stride, h, w);
+        lp.bn[2] = add_bn(ld.c_out, N * ho * wo);
+        pend.push_back({1, lp.conv[2], -1, 0, 0});
+        pend.push_back({0, -1, lp.bn[2], 0, (size_t)ld.c_out});
+        pend.push_back({0, -1, lp.bn[2], 1, (size_t)ld.c_out});
+        lp.act[3] = save(Eout);  // p
+      }
+    } else {  // pre-activation
+      lp.bn[0] = add_bn(c, N * h * w);
+      lp.conv[0] = add_conv(ld.c_out, c, 9, ld.stride, h, w);
+      lp.bn[1] = add_bn(ld.c_out, N * ho * wo);
+      lp.conv[1] = add_conv(ld.c_out, ld.c_out, 9, 1, ho, wo);
+      pend.push_back({0, -1, lp.bn[0], 0, (size_t)c});
+      pend.push_back({0, -1, lp.bn[0], 1, (size_t)c});
+      pend.push_back({1, lp.conv[0], -1, 0, 0});
+      pend.push_back({0, -1, lp.bn[1], 0, (size_t)ld.c_out});
+      pend.push_back({0, -1, lp.bn[1], 1, (size_t)ld.c_out});
+      pend.push_back({1, lp.conv[1], -1, 0, 0});
+      lp.act[0] = save(Ein);   // o1
+      lp.act[1] = save(Eout);  // c1
+      lp.act[2] = save(Eout);  // o2
+      if (lp.projects) {
+        lp.conv[2] = add_conv(ld.c_out, c, 1, ld.stride, h, w);
+        pend.push_back({1, lp.conv[2], -1, 0, 0});
+      }
+    }
+    lp.out_b = save(Eout);  // bf16 copy of the layer output (next layer's MFMA / BN operand, ReLU mask)
+    p.L.push_back(lp);
+    c = ld.c_out; h = ho; w = wo;
+  }
+  if (p.is_top) { p.out_c = 1; p.out_h = 1; p.out_w = 1 + N * desc->num_classes; }
+  else { p.out_c = c; p.out_h = h; p.out_w = w; }
+  // parameter arena: conv region, then the small tensors in external order
+  p.small_off = align_up(p.conv_elems, 4);
+  size_t soff = p.small_off;
+  for (const Pending& q : pend) {
+    ParamTensor t{};
+    t.ext_off = ext;
+    if (q.kind == 1) {
+      const ConvInfo& ci = p.convs[q.conv];
+      t.count = (size_t)ci.sh.Co * ci.sh.T * ci.sh.Ci;
+      t.int_off = ci.p_off;
+      t.conv = q.conv;
+    } else {
+      t.count = q.count;
+      t.int_off = soff;
+      t.conv = -1;
+      if (q.which == 0) p.bns[q.bn].gamma_off = soff;
+      else if (q.which == 1) p.bns[q.bn].beta_off = soff;
+      else if (q.which == 2) p.L[q.bn].fc_w_off = soff;
+      else p.L[q.bn].fc_b_off = soff;
+      soff += q.count;
+      small += q.count;
+    }
+    ext += t.count;
+    p.ptensors.push_back(t);
+  }
+  p.ext_params = ext;
+  p.small_count = align_up(small, 4);
+  p.P = p.small_off + p.small_count;
+  if (p.P >= (1ull << 31) || p.warena_elems >= (1ull << 32) || p.maxE >= (1ull << 31)) { *why = FDG_ERR_UNSUPPORTED; return false; }
+  for (const ConvInfo& ci : p.convs) p.emit_blocks += ((size_t)ci.sh.Co * ci.sh.T * ci.sh.Cip + 1023) / 1024;
+  // workspace layout
+  size_t o = 0;
+  auto take = [&](size_t bytes) { const size_t at = o; o += align_up(bytes, kAlign); return at; };
+  p.o_params = take(p.P * 4);
+  p.o_mom = take(p.P * 4);
+  p.o_grads = take(p.P * 4);
+  p.o_bsums = take(p.stat_floats * 4);     // directly after the gradients: one fill clears both
+  p.o_running = take(p.stat_floats * 4);
+  p.o_table = take(p.convs.size() * sizeof(WeightEmitEntry));
+  {  // one slot
+    size_t so = 0;
+    auto stake = [&](size_t bytes) { const size_t at = so; so += align_up(bytes, kAlign); return at; };
+    p.s_warena = stake(p.warena_elems * 2);
+    p.s_small = stake(p.small_count * 4);
+    p.s_sums = stake(p.stat_floats * 4);
+    p.s_xin = stake((size_t)N * desc->h_in * desc->w_in * p.Cp_in * 2);
+    p.s_acts = stake(act_bytes);
+    if (p.is_top) {
+      p.s_pooled = stake((size_t)N * p.head_C * 4);
+      p.s_dl = stake((size_t)N * desc->num_classes * 4);
+      p.s_logits = stake((size_t)N * desc->num_classes * 4);
+      p.s_labels = stake((size_t)N * 4);
+    }
+    p.slot_bytes = so;
+  }
+  p.o_slots = take(p.slot_bytes * (size_t)(desc->delay + 1));
+  for (int i = 0; i < 2; ++i) p.o_S[i] = take(p.maxE * 4);
+  for (int i = 0; i < 2; ++i) p.o_G[i] = take(p.maxE * 4);
+  for (int i = 0; i < 2; ++i) p.o_GB[i] = take(p.maxE * 2);
+  for (int i = 0; i < 2; ++i) p.o_T[i] = take(p.maxE * 2);
+  p.o_TP = take(p.maxE * 4);
+  p.o_dp = take(p.is_top ? (size_t)N * p.head_C * 4 : 0);
+  p.total = o;
+  *why = FDG_OK;
+  return true;
+}
+
+}  // namespace
+
+struct fdg_module {
+  Plan p;
+  char* ws = nullptr;
+  int64_t seq_fwd = 0, seq_bwd = 0;
+  bool has_grad = false;
+  hipStream_t last_stream = nullptr;
+
+  float* params() const { return reinterpret_cast<float*>(ws + p.o_params); }
+  float* mom() const { return reinterpret_cast<float*>(ws + p.o_mom); }
+  float* grads() const { return reinterpret_cast<float*>(ws + p.o_grads); }
+  float* bsums() const { return reinterpret_cast<float*>(ws + p.o_bsums); }
+  float* running() const { return reinterpret_cast<float*>(ws + p.o_running); }
+  char* slot(int64_t seq) const { return ws + p.o_slots + p.slot_bytes * (size_t)(seq % (p.d.delay + 1)); }
+  float* S(int i) const { return reinterpret_cast<float*>(ws + p.o_S[i]); }
+  float* G(int i) const { return reinterpret_cast<float*>(ws + p.o_G[i]); }
+  bf16_t* GB(int i) const { return reinterpret_cast<bf16_t*>(ws + p.o_GB[i]); }
+  bf16_t* T(int i) const { return reinterpret_cast<bf16_t*>(ws + p.o_T[i]); }
+  float* TP() const { return reinterpret_cast<float*>(ws + p.o_TP); }
+};
+
+namespace {
+
+#define FDG_TRY(expr)                      \
+  do {                                     \
+    hipError_t e__ = (expr);               \
+    if (e__ != hipSuccess) {               \
+      (void)hipGetLastError();             \
+      return FDG_ERR_HIP;                  \
+    }                                      \
+  } while (0)
+
+// views into one slot
+struct SlotView {
+  const fdg_module* m;
+  char* base;
+  bf16_t* warena() const { return reinterpret_cast<bf16_t*>(base + m->p.s_warena); }
+  bf16_t* W(const ConvInfo& c) const { return warena() + c.w_off; }
+  bf16_t* Wt(const ConvInfo& c) const { return warena() + c.wt_off; }
+  float* small() const { return reinterpret_cast<float*>(base + m->p.s_small); }
+  // snapshot of a small parameter given its offset in the parameter arena
+  float* snap(size_t arena_off) const { return small() + (arena_off - m->p.small_off); }
+  float* sums(const BnInfo& b) const { return reinterpret_cast<float*>(base + m->p.s_sums) + b.stat_off; }
+  bf16_t* xin() const { return reinterpret_cast<bf16_t*>(base + m->p.s_xin); }
+  bf16_t* act(size_t off) const { return reinterpret_cast<bf16_t*>(base + m->p.s_acts + off); }
+  float* pooled() const { return reinterpret_cast<float*>(base + m->p.s_pooled); }
+  float* dl() const { return reinterpret_cast<float*>(base + m->p.s_dl); }
+  float* logits() const { return reinterpret_cast<float*>(base + m->p.s_logits); }
+  int32_t* labels() const { return reinterpret_cast<int32_t*>(base + m->p.s_labels); }
+};
+
+hipError_t bn_stats(const SlotView& v, const BnInfo& b, const bf16_t* x, hipStream_t s) {
+  return launch_bn_stats(x, v.sums(b), b.M, b.C, s);
+}
+
+// forward apply with the CURRENT parameters; also moves the running statistics
+hipError_t bn_apply(const fdg_module* m, const SlotView& v, const BnInfo& b, const bf16_t* x, const float* res,
+                    const BnInfo* b2, const bf16_t* x2, float* out_f32, bf16_t* out_b16, hipStream_t s) {
+  BnApplyArgs a{};
+  a.x = x; a.sums = v.sums(b); a.gamma = m->params() + b.gamma_off; a.beta = m->params() + b.beta_off;
+  a.res_f32 = res;
+  if (b2) {
+    a.x2 = x2; a.sums2 = v.sums(*b2); a.gamma2 = m->params() + b2->gamma_off; a.beta2 = m->params() + b2->beta_off;
+    a.run_mean2 = m->running() + b2->stat_off; a.run_var2 = m->running() + b2->stat_off + b2->C;
+  }
+  a.out_f32 = out_f32; a.out_b16 = out_b16;
+  a.run_mean = m->running() + b.stat_off; a.run_var = m->running() + b.stat_off + b.C;
+  a.M = b.M; a.C = b.C; a.eps = m->p.d.bn_eps; a.momentum = m->p.d.bn_momentum; a.relu = 1;
+  return launch_bn_apply(a, s);
+}
+
+// backward through ReLU (mask) and BN with the slot's gamma snapshot
+hipError_t bn_backward(const fdg_module* m, const SlotView& v, const BnInfo& b, const void* dy, bool dy_f32,
+                       const bf16_t* mask, const bf16_t* x, const float* addend, float* out_f32, bf16_t* out_b16,
+                       hipStream_t s) {
+  BnBwdArgs a{};
+  a.dy = dy; a.dy_is_f32 = dy_f32 ? 1 : 0; a.mask = mask; a.x = x; a.sums = v.sums(b);
+  a.gamma = v.snap(b.gamma_off);
+  a.bsums = m->bsums() + b.stat_off;
+  a.addend = addend; a.out_f32 = out_f32; a.out_b16 = out_b16;
+  a.dgamma = m->grads() + b.gamma_off; a.dbeta = m->grads() + b.beta_off;
+  a.M = b.M; a.C = b.C; a.eps = m->p.d.bn_eps;
+  hipError_t e = launch_bn_bwd_reduce(a, s);
+  if (e != hipSuccess) return e;
+  return launch_bn_bwd_apply(a, s);
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+// C ABI
+// ------------------------------------------------------------------------------------------------
+extern "C" {
+
+size_t fdg_module_workspace_bytes(const fdg_module_desc* desc) {
+  Plan p;
+  fdg_status why;
+  if (!build_plan(desc, p, &why)) return 0;
+  return p.total;
+}
+
+fdg_status fdg_module_create(const fdg_module_desc* desc, void* dev_workspace, size_t bytes, void* hip_stream,
+                             fdg_module** out) {
+  if (!out) return FDG_ERR_INVALID_ARG;
+  *out = nullptr;
+  fdg_module* m = new (std::nothrow) fdg_module();
+  if (!m) return FDG_ERR_INVALID_ARG;
+  fdg_status why;
+  if (!build_plan(desc, m->p, &why)) {
+    delete m;
+    return why;
+  }
+  if (!dev_workspace || bytes < m->p.total || (reinterpret_cast<uintptr_t>(dev_workspace) % kAlign) != 0) {
+    delete m;
+    return dev_workspace ? FDG_ERR_WORKSPACE_TOO_SMALL : FDG_ERR_INVALID_ARG;
+  }
+  m->ws = static_cast<char*>(dev_workspace);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  m->last_stream = s;
+  const Plan& p = m->p;
+  // parameters, momentum, gradients, backward sums, running statistics (mean 0, var 1), emit table
+  hipError_t e = launch_fill_zero(m->ws, p.o_running, s);
+  if (e == hipSuccess) e = launch_fill_zero(m->ws + p.o_running, align_up(p.stat_floats * 4, kAlign), s);
+  for (const BnInfo& b : p.bns)
+    if (e == hipSuccess) e = launch_fill_f32(m->running() + b.stat_off + b.C, b.C, 1.f, s);
+  if (e == hipSuccess && !p.convs.empty()) {
+    std::vector<WeightEmitEntry> tab(p.convs.size());
+    uint32_t blk = 0;
+    for (size_t i = 0; i < p.convs.size(); ++i) {
+      const ConvInfo& c = p.convs[i];
+      tab[i].src_off = (uint32_t)c.p_off; tab[i].w_off = (uint32_t)c.w_off; tab[i].wt_off = (uint32_t)c.wt_off;
+      tab[i].Co = c.sh.Co; tab[i].T = c.sh.T; tab[i].Ci = c.sh.Ci; tab[i].Cip = c.sh.Cip;
+      tab[i].block_start = blk;
+      blk += (uint32_t)(((size_t)c.sh.Co * c.sh.T * c.sh.Cip + 1023) / 1024);
+    }
+    e = hipMemcpyAsync(m->ws + p.o_table, tab.data(), tab.size() * sizeof(WeightEmitEntry), hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);  // tab is a host temporary
+  }
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    delete m;
+    return FDG_ERR_HIP;
+  }
+  *out = m;
+  return FDG_OK;
+}
+
+void fdg_destroy(fdg_module* m) { delete m; }
+
+fdg_status fdg_forward(fdg_module* m, const float* x_dev, const int32_t* labels_dev, float* y_dev, void* hip_stream) {
+  if (!m || !x_dev || !y_dev) return FDG_ERR_INVALID_ARG;
+  const Plan& p = m->p;
+  if (p.is_top != (labels_dev != nullptr)) return FDG_ERR_INVALID_ARG;
+  if (m->seq_fwd - m->seq_bwd >= p.d.delay + 1) return FDG_ERR_QUEUE_FULL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  m->last_stream = s;
+  SlotView v{m, m->slot(m->seq_fwd)};
+  const int N = p.d.n;
+  // snapshot of the weights this forward uses (Eq. 10 evaluates the backward at these)
+  FDG_TRY(launch_emit_weights(m->params(), v.warena(), reinterpret_cast<const WeightEmitEntry*>(m->ws + p.o_table),
+                              (int)p.convs.size(), (int)p.emit_blocks, s));
+  if (p.small_count)
+    FDG_TRY(hipMemcpyAsync(v.small(), m->params() + p.small_off, p.small_count * 4, hipMemcpyDeviceToDevice, s));
+  if (p.stat_floats) FDG_TRY(launch_fill_zero(v.sums(p.bns[0]), align_up(p.stat_floats * 4, 16), s));
+  if (p.is_top) FDG_TRY(hipMemcpyAsync(v.labels(), labels_dev, (size_t)N * 4, hipMemcpyDeviceToDevice, s));
+  // module input: fp32 NCHW -> fp32 NHWC stream + bf16 NHWC copy (kept for the backward)
+  int cur = 0;
+  FDG_TRY(launch_nchw_to_nhwc(x_dev, (p.d.c_in % 8 == 0) ? m->S(cur) : nullptr, v.xin(), N, p.d.c_in, p.d.h_in * p.d.w_in,
+                              p.Cp_in, 1.f, s));
+  const bf16_t* cur_b = v.xin();
+  for (size_t li = 0; li < p.L.size(); ++li) {
+    const LayerPlan& L = p.L[li];
+    const int nxt = cur ^ 1;
+    if (L.kind == FDG_STEM_CONV_BN_RELU) {
+      const ConvInfo& c0 = p.convs[L.conv[0]];
+      const BnInfo& b0 = p.bns[L.bn[0]];
+      FDG_TRY(conv_forward(c0.sh, cur_b, v.W(c0), nullptr, nullptr, v.act(L.act[0]), s));
+      FDG_TRY(bn_stats(v, b0, v.act(L.act[0]), s));
+      FDG_TRY(bn_apply(m, v, b0, v.act(L.act[0]), nullptr, nullptr, nullptr, m->S(nxt), v.act(L.out_b), s));
+    } else if (L.kind == FDG_BASIC_POSTACT) {
+      const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]];
+      const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]];
+      bf16_t *t_c1 = v.act(L.act[0]), *t_a1 = v.act(L.act[1]), *t_c2 = v.act(L.act[2]);
+      FDG_TRY(conv_forward(c1.sh, cur_b, v.W(c1), nullptr, nullptr, t_c1, s));
+      FDG_TRY(bn_stats(v, b1, t_c1, s));
+      FDG_TRY(bn_apply(m, v, b1, t_c1, nullptr, nullptr, nullptr, nullptr, t_a1, s));
+      FDG_TRY(conv_forward(c2.sh, t_a1, v.W(c2), nullptr, nullptr, t_c2, s));
+      FDG_TRY(bn_stats(v, b2, t_c2, s));
+      if (L.projects) {
+        const ConvInfo& cp = p.convs[L.conv[2]];
+        const BnInfo& bp = p.bns[L.bn[2]];
+        bf16_t* t_p = v.act(L.act[3]);
+        FDG_TRY(conv_forward(cp.sh, cur_b, v.W(cp), nullptr, nullptr, t_p, s));
+        FDG_TRY(bn_stats(v, bp, t_p, s));
+        FDG_TRY(bn_apply(m, v, b2, t_c2, nullptr, &bp, t_p, m->S(nxt), v.act(L.out_b), s));
+      } else {
+        FDG_TRY(bn_apply(m, v, b2, t_c2, m->S(cur), nullptr, nullptr, m->S(nxt), v.act(L.out_b), s));
+      }
+    } else if (L.kind == FDG_BASIC_PREACT) {
+      const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]];
+      const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]];
+      bf16_t *t_o1 = v.act(L.act[0]), *t_c1 = v.act(L.act[1]), *t_o2 = v.act(L.act[2]);
+      FDG_TRY(bn_stats(v, b1, cur_b, s));
+      FDG_TRY(bn_apply(m, v, b1, cur_b, nullptr, nullptr, nullptr, nullptr, t_o1, s));
+      FDG_TRY(conv_forward(c1.sh, t_o1, v.W(c1), nullptr, nullptr, t_c1, s));
+      FDG_TRY(bn_stats(v, b2, t_c1, s));
+      FDG_TRY(bn_apply(m, v, b2, t_c1, nullptr, nullptr, nullptr, nullptr, t_o2, s));
+      const float* shortcut = m->S(cur);
+      if (L.projects) {
+        const ConvInfo& cp = p.convs[L.conv[2]];
+        FDG_TRY(conv_forward(cp.sh, t_o1, v.W(cp), nullptr, m->TP(), nullptr, s));
+        shortcut = m->TP();
+      }
+      FDG_TRY(conv_forward(c2.sh, t_o2, v.W(c2), shortcut, m->S(nxt), v.act(L.out_b), s));
+    } else {  // heads
+      const bf16_t* o = cur_b;
+      if (L.kind == FDG_HEAD_PREACT) {
+        const BnInfo& b0 = p.bns[L.bn[0]];
+        FDG_TRY(bn_stats(v, b0, cur_b, s));
+        FDG_TRY(bn_apply(m, v, b0, cur_b, nullptr, nullptr, nullptr, nullptr, v.act(L.act[0]), s));
+        o = v.act(L.act[0]);
+      }
+      const int J = p.d.num_classes;
+      FDG_TRY(launch_avgpool(o, v.pooled(), N, p.head_HW, p.head_C, s));
+      FDG_TRY(launch_fc_fwd(v.pooled(), m->params() + L.fc_w_off, m->params() + L.fc_b_off, v.logits(), N, p.head_C, J, s));
+      FDG_TRY(launch_softmax_ce(v.logits(), v.labels(), y_dev, v.dl(), N, J, s));
+      break;
+    }
+    cur = nxt;
+    cur_b = v.act(L.out_b);
+  }
+  if (!p.is_top) FDG_TRY(launch_nhwc_to_nchw(m->S(cur), y_dev, N, p.out_c, p.out_h * p.out_w, p.out_c, s));
+  ++m->seq_fwd;
+  return FDG_OK;
+}
+
+fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float* grad_in_dev, void* hip_stream) {
+  if (!m) return FDG_ERR_INVALID_ARG;
+  const Plan& p = m->p;
+  if (p.is_top ? grad_out_dev != nullptr : grad_out_dev == nullptr) return FDG_ERR_INVALID_ARG;
+  if (m->seq_fwd == m->seq_bwd) return FDG_ERR_QUEUE_EMPTY;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  m->last_stream = s;
+  SlotView v{m, m->slot(m->seq_bwd)};  // the OLDEST saved forward
+  const int N = p.d.n;
+  // gradients and backward sums start at zero (weight gradients accumulate with atomics)
+  FDG_TRY(launch_fill_zero(m->ws + p.o_grads, p.o_running - p.o_grads, s));
+  int cur = 0;
+  if (!p.is_top)  // gradient shrinking of Eq. 15: multiply by beta before anything else
+    FDG_TRY(launch_nchw_to_nhwc(grad_out_dev, m->G(cur), m->GB(cur), N, p.out_c, p.out_h * p.out_w, p.out_c, p.d.beta, s));
+  for (int li = (int)p.L.size() - 1; li >= 0; --li) {
+    const LayerPlan& L = p.L[li];
+    const int nxt = cur ^ 1;
+    const bf16_t* in_b = li == 0 ? v.xin() : v.act(p.L[li - 1].out_b);  // bf16 copy of this layer's input
+    const bool need_dx = !(li == 0 && p.d.is_bottom);
+    if (L.kind == FDG_HEAD_POSTACT || L.kind == FDG_HEAD_PREACT) {
+      const int J = p.d.num_classes;
+      float* dp = reinterpret_cast<float*>(m->ws + p.o_dp);
+      FDG_TRY(launch_fc_bwd(v.pooled(), v.snap(L.fc_w_off), v.dl(), m->grads() + L.fc_w_off, m->grads() + L.fc_b_off, dp, N,
+                            p.head_C, J, s));
+      if (L.kind == FDG_HEAD_PREACT) {
+        const BnInfo& b0 = p.bns[L.bn[0]];
+        FDG_TRY(launch_pool_bwd(dp, m->TP(), nullptr, N, p.head_HW, p.head_C, s));
+        FDG_TRY(bn_backward(m, v, b0, m->TP(), true, v.act(L.act[0]), in_b, nullptr, m->G(nxt), m->GB(nxt), s));
+      } else {
+        FDG_TRY(launch_pool_bwd(dp, m->G(nxt), m->GB(nxt), N, p.head_HW, p.head_C, s));
+      }
+    } else if (L.kind == FDG_STEM_CONV_BN_RELU) {
+      const ConvInfo& c0 = p.convs[L.conv[0]];
+      const BnInfo& b0 = p.bns[L.bn[0]];
+      FDG_TRY(bn_backward(m, v, b0, m->G(cur), true, v.act(L.out_b), v.act(L.act[0]), nullptr, nullptr, m->T(0), s));
+      FDG_TRY(conv_wgrad(c0.sh, in_b, m->T(0), m->grads() + c0.p_off, s));
+      if (need_dx) FDG_TRY(conv_dgrad(c0.sh, m->T(0), v.Wt(c0), nullptr, nullptr, m->G(nxt), m->GB(nxt), s));
+    } else if (L.kind == FDG_BASIC_POSTACT) {
+      const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]];
+      const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]];
+      const bf16_t *t_c1 = v.act(L.act[0]), *t_a1 = v.act(L.act[1]), *t_c2 = v.act(L.act[2]), *t_y = v.act(L.out_b);
+      // final ReLU mask (y > 0) then BN2
+      FDG_TRY(bn_backward(m, v, b2, m->G(cur), true, t_y, t_c2, nullptr, nullptr, m->T(0), s));
+      FDG_TRY(conv_wgrad(c2.sh, t_a1, m->T(0), m->grads() + c2.p_off, s));
+      FDG_TRY(conv_dgrad(c2.sh, m->T(0), v.Wt(c2), nullptr, nullptr, nullptr, m->T(1), s));
+      FDG_TRY(bn_backward(m, v, b1, m->T(1), false, t_a1, t_c1, nullptr, nullptr, m->T(0), s));
+      FDG_TRY(conv_wgrad(c1.sh, in_b, m->T(0), m->grads() + c1.p_off, s));
+      if (L.projects) {
+        const ConvInfo& cp = p.convs[L.conv[2]];
+        const BnInfo& bp = p.bns[L.bn[2]];
+        FDG_TRY(bn_backward(m, v, bp, m->G(cur), true, t_y, v.act(L.act[3]), nullptr, nullptr, m->T(1), s));
+        FDG_TRY(conv_wgrad(cp.sh, in_b, m->T(1), m->grads() + cp.p_off, s));
+        if (need_dx) {
+          FDG_TRY(conv_dgrad(cp.sh, m->T(1), v.Wt(cp), nullptr, nullptr, m->TP(), nullptr, s));
+          FDG_TRY(conv_dgrad(c1.sh, m->T(0), v.Wt(c1), m->TP(), nullptr, m->G(nxt), m->GB(nxt), s));
+        }
+      } else if (need_dx) {
+        // identity shortcut: the masked incoming gradient joins the branch gradient
+        FDG_TRY(conv_dgrad(c1.sh, m->T(0), v.Wt(c1), m->G(cur), t_y, m->G(nxt), m->GB(nxt), s));
+      }
+    } else {  // pre-activation block: y = conv2(o2) + shortcut
+      const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]];
+      const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]];
+      const bf16_t *t_o1 = v.act(L.act[0]), *t_c1 = v.act(L.act[1]), *t_o2 = v.act(L.act[2]);
+      FDG_TRY(conv_wgrad(c2.sh, t_o2, m->GB(cur), m->grads() + c2.p_off, s));
+      FDG_TRY(conv_dgrad(c2.sh, m->GB(cur), v.Wt(c2), nullptr, nullptr, nullptr, m->T(0), s));
+      FDG_TRY(bn_backward(m, v, b2, m->T(0), false, t_o2, t_c1, nullptr, nullptr, m->T(1), s));
+      FDG_TRY(conv_wgrad(c1.sh, t_o1, m->T(1), m->grads() + c1.p_off, s));
+      if (L.projects) {
+        const ConvInfo& cp = p.convs[L.conv[2]];
+        FDG_TRY(conv_wgrad(cp.sh, t_o1, m->GB(cur), m->grads() + cp.p_off, s));
+        FDG_TRY(conv_dgrad(cp.sh, m->GB(cur), v.Wt(cp), nullptr, nullptr, m->TP(), nullptr, s));
+        FDG_TRY(conv_dgrad(c1.sh, m->T(1), v.Wt(c1), m->TP(), nullptr, nullptr, m->T(0), s));
+        FDG_TRY(bn_backward(m, v, b1, m->T(0), false, t_o1, in_b, nullptr, need_dx ? m->G(nxt) : nullptr,
+                            need_dx ? m->GB(nxt) : nullptr, s));
+      } else {
+        FDG_TRY(conv_dgrad(c1.sh, m->T(1), v.Wt(c1), nullptr, nullptr, nullptr, m->T(0), s));
+        FDG_TRY(bn_backward(m, v, b1, m->T(0), false, t_o1, in_b, m->G(cur), need_dx ? m->G(nxt) : nullptr,
+                            need_dx ? m->GB(nxt) : nullptr, s));
+      }
+    }
+    cur = nxt;
+  }
+  if (grad_in_dev && !p.d.is_bottom)
+    FDG_TRY(launch_nhwc_to_nchw(m->G(cur), grad_in_dev, N, p.d.c_in, p.d.h_in * p.d.w_in, p.Cp_in, s));
+  ++m->seq_bwd;
+  m->has_grad = true;
+  return FDG_OK;
+}
+
+fdg_status fdg_update(fdg_module* m, float lr, void* hip_stream) {
+  if (!m) return FDG_ERR_INVALID_ARG;
+  if (!m->has_grad) return FDG_ERR_NO_GRAD;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  m->last_stream = s;
+  FDG_TRY(launch_sgd(m->params(), m->mom(), m->grads(), m->p.P, lr, m->p.d.momentum, m->p.d.weight_decay, s));
+  m->has_grad = false;
+  return FDG_OK;
+}
+
+size_t fdg_param_count(const fdg_module* m) { return m ? m->p.ext_params : 0; }
+
+// external flat order <-> internal arena order
+static void ext_to_int(const Plan& p, const float* ext, float* in) {
+  for (const ParamTensor& t : p.ptensors) {
+    if (t.conv < 0) {
+      for (size_t i = 0; i < t.count; ++i) in[t.int_off + i] = ext[t.ext_off + i];
+    } else {
+      const ConvShape& c = p.convs[t.conv].sh;
+      for (int co = 0; co < c.Co; ++co)
+        for (int ci = 0; ci < c.Ci; ++ci)
+          for (int k = 0; k < c.T; ++k)
+            in[t.int_off + ((size_t)co * c.T + k) * c.Ci + ci] = ext[t.ext_off + ((size_t)co * c.Ci + ci) * c.T + k];
+    }
+  }
+}
+static void int_to_ext(const Plan& p, const float* in, float* ext) {
+  for (const ParamTensor& t : p.ptensors) {
+    if (t.conv < 0) {
+      for (size_t i = 0; i < t.count; ++i) ext[t.ext_off + i] = in[t.int_off + i];
+    } else {
+      const ConvShape& c = p.convs[t.conv].sh;
+      for (int co = 0; co < c.Co; ++co)
+        for (int ci = 0; ci < c.Ci; ++ci)
+          for (int k = 0; k < c.T; ++k)
+            ext[t.ext_off + ((size_t)co * c.Ci + ci) * c.T + k] = in[t.int_off + ((size_t)co * c.T + k) * c.Ci + ci];
+    }
+  }
+}
+
+fdg_status fdg_set_params(fdg_module* m, const float* host_src, size_t count) {
+  if (!m || !host_src || count != m->p.ext_params) return FDG_ERR_INVALID_ARG;
+  std::vector<float> buf(m->p.P, 0.f);
+  ext_to_int(m->p, host_src, buf.data());
+  FDG_TRY(hipStreamSynchronize(m->last_stream));
+  FDG_TRY(hipMemcpy(m->params(), buf.data(), m->p.P * 4, hipMemcpyHostToDevice));
+  FDG_TRY(hipMemset(m->mom(), 0, m->p.P * 4));
+  FDG_TRY(hipDeviceSynchronize());
+  return FDG_OK;
+}
+
+static fdg_status read_arena(const fdg_module* m, const float* dev, float* host_dst, size_t count) {
+  if (!m || !host_dst || count != m->p.ext_params) return FDG_ERR_INVALID_ARG;
+  std::vector<float> buf(m->p.P);
+  FDG_TRY(hipStreamSynchronize(m->last_stream));
+  FDG_TRY(hipMemcpy(buf.data(), dev, m->p.P * 4, hipMemcpyDeviceToHost));
+  int_to_ext(m->p, buf.data(), host_dst);
+  return FDG_OK;
+}
+fdg_status fdg_get_params(const fdg_module* m, float* host_dst, size_t count) {
+  return read_arena(m, m ? m->params() : nullptr, host_dst, count);
+}
+fdg_status fdg_get_grads(const fdg_module* m, float* host_dst, size_t count) {
+  return read_arena(m, m ? m->grads() : nullptr, host_dst, count);
+}
+fdg_status fdg_get_momentum(const fdg_module* m, float* host_dst, size_t count) {
+  return read_arena(m, m ? m->mom() : nullptr, host_dst, count);
+}
+
+size_t fdg_bn_stat_count(const fdg_module* m) { return m ? m->p.stat_floats : 0; }
+fdg_status fdg_get_bn_running(const fdg_module* m, float* host_dst, size_t count) {
+  if (!m || !host_dst || count != m->p.stat_floats) return FDG_ERR_INVALID_ARG;
+  if (count == 0) return FDG_OK;
+  // the arena holds the BNs in creation order; report them in parameter order
+  std::vector<float> buf(count);
+  FDG_TRY(hipStreamSynchronize(m->last_stream));
+  FDG_TRY(hipMemcpy(buf.data(), m->running(), count * 4, hipMemcpyDeviceToHost));
+  size_t o = 0;
+  for (const ParamTensor& t : m->p.ptensors) {
+    if (t.conv >= 0) continue;
+    for (const BnInfo& b : m->p.bns)
+      if (b.gamma_off == t.int_off) {
+        for (int i = 0; i < 2 * b.C; ++i) host_dst[o++] = buf[b.stat_off + i];
+        break;
+      }
+  }
+  return o == count ? FDG_OK : FDG_ERR_INVALID_ARG;
+}
+
+fdg_status fdg_output_shape(const fdg_module* m, int32_t out[4]) {
+  if (!m || !out) return FDG_ERR_INVALID_ARG;
+  out[0] = m->p.is_top ? 1 : m->p.d.n;
+  out[1] = m->p.out_c; out[2] = m->p.out_h; out[3] = m->p.out_w;
+  return FDG_OK;
+}
+
+fdg_status fdg_queue_state(const fdg_module* m, int32_t* outstanding, int64_t* oldest_seq, int64_t* newest_seq) {
+  if (!m) return FDG_ERR_INVALID_ARG;
+  const int64_t n = m->seq_fwd - m->seq_bwd;
+  if (outstanding) *outstanding = (int32_t)n;
+  if (oldest_seq) *oldest_seq = n ? m->seq_bwd : -1;
+  if (newest_seq) *newest_seq = n ? m->seq_fwd - 1 : -1;
+  return FDG_OK;
+}
+
+const char* fdg_status_string(fdg_status s) {
+  switch (s) {
+    case FDG_OK: return "ok";
+    case FDG_ERR_INVALID_ARG: return "invalid argument";
+    case FDG_ERR_UNSUPPORTED: return "unsupported layer shape";
+    case FDG_ERR_WORKSPACE_TOO_SMALL: return "workspace too small or misaligned";
+    case FDG_ERR_QUEUE_FULL: return "history queue full";
+    case FDG_ERR_QUEUE_EMPTY: return "history queue empty";
+    case FDG_ERR_NO_GRAD: return "no gradient since the last update";
+    case FDG_ERR_HIP: return "HIP error";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,556 @@
+// Bandwidth-bound kernels of the FDG module step: batch normalisation (forward statistics / apply,
+// backward reduce / apply), layout changes at the module boundary, the classification head, the
+// momentum-SGD update of Eq. 11 and the bf16 weight snapshot.  All tensors are NHWC [M, C]; a thread
+// always owns 8 consecutive channels of one pixel (one 16-byte bf16 access), so a wavefront reads
+// whole contiguous rows.
+#include "fdg_internal.h"
+
+namespace fdg {
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __builtin_bit_cast(float, u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __builtin_bit_cast(float, u & 0xffff0000u); }
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  bf16_t l = (bf16_t)lo, h = (bf16_t)hi;
+  return (uint32_t)__builtin_bit_cast(uint16_t, l) | ((uint32_t)__builtin_bit_cast(uint16_t, h) << 16);
+}
+__device__ __forceinline__ void unpack8(const uint4& u, float (&f)[8]) {
+  f[0] = bf16_lo(u.x); f[1] = bf16_hi(u.x); f[2] = bf16_lo(u.y); f[3] = bf16_hi(u.y);
+  f[4] = bf16_lo(u.z); f[5] = bf16_hi(u.z); f[6] = bf16_lo(u.w); f[7] = bf16_hi(u.w);
+}
+__device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
+  return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+}
+__device__ __forceinline__ void load8_f32(const float* p, float (&f)[8]) {
+  const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+  f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+}
+__device__ __forceinline__ void store8_f32(float* p, const float (&f)[8]) {
+  *reinterpret_cast<float4*>(p) = make_float4(f[0], f[1], f[2], f[3]);
+  *reinterpret_cast<float4*>(p + 4) = make_float4(f[4], f[5], f[6], f[7]);
+}
+
+constexpr int kThreads = 256;
+
+// Column reduction helper.  Threads are laid out as (row lane r, channel group cg) with cg fastest;
+// each thread holds NV partial sums for its 8 channels.  Partials of equal cg are added through LDS
+// and the first row lane adds the block result to global memory.
+template <int NV>
+__device__ __forceinline__ void block_reduce_to_global(float (&v)[NV][8], float* const (&dst)[NV], int cg, int r, int CG,
+                                                       int R, float* smem /* [R*CG*8] */) {
+#pragma unroll
+  for (int q = 0; q < NV; ++q) {
+    __syncthreads();
+    if (cg < CG && r < R) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) smem[(r * CG + cg) * 8 + i] = v[q][i];
+    }
+    __syncthreads();
+    // CG*8 columns, summed over R rows
+    for (int col = threadIdx.x; col < CG * 8; col += blockDim.x) {
+      float s = 0.f;
+      for (int rr = 0; rr < R; ++rr) s += smem[rr * CG * 8 + col];
+      atomicAdd(dst[q] + col, s);
+    }
+  }
+}
+
+// ---- BN forward statistics: sums[c] += sum x, sums[C + c] += sum x^2 --------------------------------
+__global__ __launch_bounds__(kThreads) void bn_stats_kernel(const bf16_t* __restrict__ x, float* __restrict__ sums, int M,
+                                                            int C, int rows_per_block) {
+  extern __shared__ float smem[];
+  const int CG = C >> 3, R = kThreads / CG;
+  const int cg = threadIdx.x % CG, r = threadIdx.x / CG;
+  float v[2][8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[0][i] = v[1][i] = 0.f;
+  const int row_lo = blockIdx.x * rows_per_block, row_hi = min(M, row_lo + rows_per_block);
+  if (r < R) {
+    for (int row = row_lo + r; row < row_hi; row += R) {
+      float f[8];
+      unpack8(*reinterpret_cast<const uint4*>(x + (size_t)row * C + cg * 8), f);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        v[0][i] += f[i];
+        v[1][i] += f[i] * f[i];
+      }
+    }
+  }
+  float* const dst[2] = {sums, sums + C};
+  block_reduce_to_global<2>(v, dst, cg, r, CG, R, smem);
+}
+
+static int reduce_grid(int M, int C, int* rows_per_block) {
+  const int CG = C / 8, R = kThreads / CG;
+  int blocks = (M + R * 4 - 1) / (R * 4);  // at least 4 rows per thread
+  if (blocks > 1024) blocks = 1024;
+  if (blocks < 1) blocks = 1;
+  int rpb = (M + blocks - 1) / blocks;
+  rpb = (rpb + R - 1) / R * R;
+  *rows_per_block = rpb;
+  return (M + rpb - 1) / rpb;
+}
+
+hipError_t launch_bn_stats(const bf16_t* x, float* sums, int M, int C, hipStream_t s) {
+  if (C % 8 != 0 || C > 2048 || M <= 0) return hipErrorInvalidValue;
+  int rpb;
+  const int blocks = reduce_grid(M, C, &rpb);
+  hipLaunchKernelGGL(bn_stats_kernel, dim3(blocks), dim3(kThreads), kThreads * 8 * sizeof(float), s, x, sums, M, C, rpb);
+  return hipGetLastError();
+}
+
+// ---- BN apply: y = relu?( gamma*xhat + beta [+ res] [+ gamma2*xhat2 + beta2] ) ------------------------
+// scale/shift per channel are derived once per block from the accumulated sums.
+__device__ __forceinline__ void bn_coeffs(const float* sums, const float* gamma, const float* beta, int C, float invM,
+                                          float eps, float* sc, float* sh) {
+  for (int c = threadIdx.x; c < C; c += blockDim.x) {
+    const float mean = sums[c] * invM;
+    const float var = fmaxf(sums[C + c] * invM - mean * mean, 0.f);
+    const float is = rsqrtf(var + eps);
+    const float g = gamma[c] * is;
+    sc[c] = g;
+    sh[c] = beta[c] - mean * g;
+  }
+}
+__device__ __forceinline__ void bn_running(const float* sums, float* run_mean, float* run_var, int C, int M, float mom) {
+  const float invM = 1.f / (float)M;
+  const float unbias = M > 1 ? (float)M / (float)(M - 1) : 1.f;
+  for (int c = threadIdx.x; c < C; c += blockDim.x) {
+    const float mean = sums[c] * invM;
+    const float var = fmaxf(sums[C + c] * invM - mean * mean, 0.f);
+    run_mean[c] = (1.f - mom) * run_mean[c] + mom * mean;
+    run_var[c] = (1.f - mom) * run_var[c] + mom * var * unbias;
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void bn_apply_kernel(BnApplyArgs a) {
+  extern __shared__ float smem[];  // sc[C], sh[C], sc2[C], sh2[C]
+  const int C = a.C, CG = C >> 3;
+  float *sc = smem, *sh = smem + C, *sc2 = smem + 2 * C, *sh2 = smem + 3 * C;
+  const float invM = 1.f / (float)a.M;
+  bn_coeffs(a.sums, a.gamma, a.beta, C, invM, a.eps, sc, sh);
+  if (a.x2) bn_coeffs(a.sums2, a.gamma2, a.beta2, C, invM, a.eps, sc2, sh2);
+  if (blockIdx.x == 0) {
+    if (a.run_mean) bn_running(a.sums, a.run_mean, a.run_var, C, a.M, a.momentum);
+    if (a.x2 && a.run_mean2) bn_running(a.sums2, a.run_mean2, a.run_var2, C, a.M, a.momentum);
+  }
+  __syncthreads();
+  const size_t units = (size_t)a.M * CG;
+  for (size_t uidx = (size_t)blockIdx.x * kThreads + threadIdx.x; uidx < units; uidx += (size_t)gridDim.x * kThreads) {
+    const int cg = (int)(uidx % CG);
+    const size_t o = uidx * 8;
+    float f[8];
+    unpack8(*reinterpret_cast<const uint4*>(a.x + o), f);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) f[i] = f[i] * sc[cg * 8 + i] + sh[cg * 8 + i];
+    if (a.res_f32) {
+      float rr[8];
+      load8_f32(a.res_f32 + o, rr);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) f[i] += rr[i];
+    }
+    if (a.x2) {
+      float g[8];
+      unpack8(*reinterpret_cast<const uint4*>(a.x2 + o), g);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) f[i] += g[i] * sc2[cg * 8 + i] + sh2[cg * 8 + i];
+    }
+    if (a.relu) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) f[i] = fmaxf(f[i], 0.f);
+    }
+    if (a.out_f32) store8_f32(a.out_f32 + o, f);
+    if (a.out_b16) *reinterpret_cast<uint4*>(a.out_b16 + o) = pack8(f);
+  }
+}
+
+static int stream_grid(size_t units) {
+  size_t b = (units + kThreads - 1) / kThreads;
+  if (b > 2048) b = 2048;
+  if (b < 1) b = 1;
+  return (int)b;
+}
+
+hipError_t launch_bn_apply(const BnApplyArgs& a, hipStream_t s) {
+  if (a.C % 8 != 0 || a.C > 2048 || a.M <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(bn_apply_kernel, dim3(stream_grid((size_t)a.M * (a.C / 8))), dim3(kThreads),
+                     4 * a.C * sizeof(float), s, a);
+  return hipGetLastError();
+}
+
+// ---- BN backward ---------------------------------------------------------------------------------
+// mean / invstd per channel from the forward sums, into LDS
+__device__ __forceinline__ void bn_moments(const float* sums, int C, float invM, float eps, float* mean, float* is) {
+  for (int c = threadIdx.x; c < C; c += blockDim.x) {
+    const float mu = sums[c] * invM;
+    const float var = fmaxf(sums[C + c] * invM - mu * mu, 0.f);
+    mean[c] = mu;
+    is[c] = rsqrtf(var + eps);
+  }
+}
+
+template <bool DY_F32>
+__device__ __forceinline__ void load_masked_dy(const void* dy, const bf16_t* mask, size_t o, float (&g)[8]) {
+  if (DY_F32)
+    load8_f32(reinterpret_cast<const float*>(dy) + o, g);
+  else
+    unpack8(*reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(dy) + o), g);
+  float mk[8];
+  unpack8(*reinterpret_cast<const uint4*>(mask + o), mk);
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+    if (!(mk[i] > 0.f)) g[i] = 0.f;
+}
+
+template <bool DY_F32>
+__global__ __launch_bounds__(kThreads) void bn_bwd_reduce_kernel(BnBwdArgs a, int rows_per_block) {
+  extern __shared__ float smem[];  // max(2C, 256*8)
+  const int C = a.C, CG = C >> 3, R = kThreads / CG;
+  const int cg = threadIdx.x % CG, r = threadIdx.x / CG;
+  float* mean = smem;
+  float* is = smem + C;
+  bn_moments(a.sums, C, 1.f / (float)a.M, a.eps, mean, is);
+  __syncthreads();
+  float mu[8], iv[8];
+  if (r < R) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      mu[i] = mean[cg * 8 + i];
+      iv[i] = is[cg * 8 + i];
+    }
+  }
+  float v[2][8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[0][i] = v[1][i] = 0.f;
+  const int row_lo = blockIdx.x * rows_per_block, row_hi = min(a.M, row_lo + rows_per_block);
+  if (r < R) {
+    for (int row = row_lo + r; row < row_hi; row += R) {
+      const size_t o = (size_t)row * C + cg * 8;
+      float g[8], xv[8];
+      load_masked_dy<DY_F32>(a.dy, a.mask, o, g);
+      unpack8(*reinterpret_cast<const uint4*>(a.x + o), xv);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        v[0][i] += g[i];
+        v[1][i] += g[i] * ((xv[i] - mu[i]) * iv[i]);
+      }
+    }
+  }
+  float* const dst[2] = {a.bsums, a.bsums + C};
+  block_reduce_to_global<2>(v, dst, cg, r, CG, R, smem);
+}
+
+hipError_t launch_bn_bwd_reduce(const BnBwdArgs& a, hipStream_t s) {
+  if (a.C % 8 != 0 || a.C > 2048 || a.M <= 0 || !a.mask) return hipErrorInvalidValue;
+  int rpb;
+  const int blocks = reduce_grid(a.M, a.C, &rpb);
+  size_t sm = (size_t)kThreads * 8 * sizeof(float);
+  if (sm < 2 * (size_t)a.C * sizeof(float)) sm = 2 * (size_t)a.C * sizeof(float);
+  if (a.dy_is_f32)
+    hipLaunchKernelGGL(bn_bwd_reduce_kernel<true>, dim3(blocks), dim3(kThreads), sm, s, a, rpb);
+  else
+    hipLaunchKernelGGL(bn_bwd_reduce_kernel<false>, dim3(blocks), dim3(kThreads), sm, s, a, rpb);
+  return hipGetLastError();
+}
+
+// dx = gamma*invstd*(g - S1/M - xhat*S2/M) [+ addend];  dgamma = S2, dbeta = S1
+template <bool DY_F32>
+__global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(BnBwdArgs a) {
+  extern __shared__ float smem[];  // mean[C], is[C], k1[C] (= S1/M), k2[C] (= S2/M), gi[C] (= gamma*is)
+  const int C = a.C, CG = C >> 3;
+  float *mean = smem, *is = smem + C, *k1 = smem + 2 * C, *k2 = smem + 3 * C, *gi = smem + 4 * C;
+  const float invM = 1.f / (float)a.M;
+  bn_moments(a.sums, C, invM, a.eps, mean, is);
+  __syncthreads();
+  for (int c = threadIdx.x; c < C; c += blockDim.x) {
+    const float s1 = a.bsums[c], s2 = a.bsums[C + c];
+    k1[c] = s1 * invM;
+    k2[c] = s2 * invM;
+    gi[c] = a.gamma[c] * is[c];
+    if (blockIdx.x == 0) {
+      a.dbeta[c] = s1;
+      a.dgamma[c] = s2;
+    }
+  }
+  __syncthreads();
+  if (!a.out_f32 && !a.out_b16) return;
+  const size_t units = (size_t)a.M * CG;
+  for (size_t uidx = (size_t)blockIdx.x * kThreads + threadIdx.x; uidx < units; uidx += (size_t)gridDim.x * kThreads) {
+    const int c0 = (int)(uidx % CG) * 8;
+    const size_t o = uidx * 8;
+    float g[8], xv[8];
+    load_masked_dy<DY_F32>(a.dy, a.mask, o, g);
+    unpack8(*reinterpret_cast<const uint4*>(a.x + o), xv);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float xh = (xv[i] - mean[c0 + i]) * is[c0 + i];
+      g[i] = gi[c0 + i] * (g[i] - k1[c0 + i] - xh * k2[c0 + i]);
+    }
+    if (a.addend) {
+      float ad[8];
+      load8_f32(a.addend + o, ad);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) g[i] += ad[i];
+    }
+    if (a.out_f32) store8_f32(a.out_f32 + o, g);
+    if (a.out_b16) *reinterpret_cast<uint4*>(a.out_b16 + o) = pack8(g);
+  }
+}
+
+hipError_t launch_bn_bwd_apply(const BnBwdArgs& a, hipStream_t s) {
+  if (a.C % 8 != 0 || a.C > 2048 || a.M <= 0 || !a.mask) return hipErrorInvalidValue;
+  const int grid = (a.out_f32 || a.out_b16) ? stream_grid((size_t)a.M * (a.C / 8)) : 1;
+  const size_t sm = 5 * (size_t)a.C * sizeof(float);
+  if (a.dy_is_f32)
+    hipLaunchKernelGGL(bn_bwd_apply_kernel<true>, dim3(grid), dim3(kThreads), sm, s, a);
+  else
+    hipLaunchKernelGGL(bn_bwd_apply_kernel<false>, dim3(grid), dim3(kThreads), sm, s, a);
+  return hipGetLastError();
+}
+
+// ---- layout changes at the module boundary -----------------------------------------------------
+// src fp32 [N, C, HW] -> dst [N, HW, Cp] (channels >= C are zero), scaled.  32x32 tiles through LDS.
+__global__ __launch_bounds__(kThreads) void nchw_to_nhwc_kernel(const float* __restrict__ src, float* __restrict__ dst_f32,
+                                                                bf16_t* __restrict__ dst_b16, int C, int HW, int Cp,
+                                                                float scale) {
+  __shared__ float tile[32][33];
+  const int n = blockIdx.z, hw0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+  for (int i = ty; i < 32; i += 8) {
+    const int c = c0 + i, hw = hw0 + tx;
+    tile[i][tx] = (c < C && hw < HW) ? src[((size_t)n * C + c) * HW + hw] * scale : 0.f;
+  }
+  __syncthreads();
+  for (int i = ty; i < 32; i += 8) {
+    const int hw = hw0 + i, c = c0 + tx;
+    if (hw < HW && c < Cp) {
+      const float v = tile[tx][i];
+      const size_t o = ((size_t)n * HW + hw) * Cp + c;
+      if (dst_f32) dst_f32[o] = v;
+      if (dst_b16) dst_b16[o] = (bf16_t)v;
+    }
+  }
+}
+
+hipError_t launch_nchw_to_nhwc(const float* src, float* dst_f32, bf16_t* dst_b16, int N, int C, int HW, int Cp,
+                               float scale, hipStream_t s) {
+  dim3 grid((HW + 31) / 32, (Cp + 31) / 32, N);
+  hipLaunchKernelGGL(nchw_to_nhwc_kernel, grid, dim3(kThreads), 0, s, src, dst_f32, dst_b16, C, HW, Cp, scale);
+  return hipGetLastError();
+}
+
+// src fp32 [N, HW, Cp] -> dst [N, C, HW]
+__global__ __launch_bounds__(kThreads) void nhwc_to_nchw_kernel(const float* __restrict__ src, float* __restrict__ dst, int C,
+                                                                int HW, int Cp) {
+  __shared__ float tile[32][33];
+  const int n = blockIdx.z, hw0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  for (int i = ty; i < 32; i += 8) {
+    const int hw = hw0 + i, c = c0 + tx;
+    tile[i][tx] = (hw < HW && c < C) ? src[((size_t)n * HW + hw) * Cp + c] : 0.f;
+  }
+  __syncthreads();
+  for (int i = ty; i < 32; i += 8) {
+    const int c = c0 + i, hw = hw0 + tx;
+    if (c < C && hw < HW) dst[((size_t)n * C + c) * HW + hw] = tile[tx][i];
+  }
+}
+
+hipError_t launch_nhwc_to_nchw(const float* src, float* dst, int N, int C, int HW, int Cp, hipStream_t s) {
+  dim3 grid((HW + 31) / 32, (C + 31) / 32, N);
+  hipLaunchKernelGGL(nhwc_to_nchw_kernel, grid, dim3(kThreads), 0, s, src, dst, C, HW, Cp);
+  return hipGetLastError();
+}
+
+// ---- head -------------------------------------------------------------------------------------------
+__global__ void avgpool_kernel(const bf16_t* __restrict__ o, float* __restrict__ pooled, int N, int HW, int C) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= N * C) return;
+  const int n = idx / C, c = idx % C;
+  float s = 0.f;
+  for (int p = 0; p < HW; ++p) s += (float)o[((size_t)n * HW + p) * C + c];
+  pooled[idx] = s / (float)HW;
+}
+hipError_t launch_avgpool(const bf16_t* o, float* pooled, int N, int HW, int C, hipStream_t s) {
+  hipLaunchKernelGGL(avgpool_kernel, dim3((N * C + 255) / 256), dim3(256), 0, s, o, pooled, N, HW, C);
+  return hipGetLastError();
+}
+
+__global__ void fc_fwd_kernel(const float* __restrict__ pooled, const float* __restrict__ W, const float* __restrict__ b,
+                              float* __restrict__ logits, int N, int C, int J) {
+  // one wavefront per (n, j)
+  const int gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
+  if (gw >= N * J) return;
+  const int n = gw / J, j = gw % J;
+  float s = 0.f;
+  for (int c = lane; c < C; c += 64) s += pooled[(size_t)n * C + c] * W[(size_t)j * C + c];
+  for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
+  if (lane == 0) logits[gw] = s + b[j];
+}
+hipError_t launch_fc_fwd(const float* pooled, const float* W, const float* b, float* logits, int N, int C, int J,
+                         hipStream_t s) {
+  hipLaunchKernelGGL(fc_fwd_kernel, dim3((N * J * 64 + 255) / 256), dim3(256), 0, s, pooled, W, b, logits, N, C, J);
+  return hipGetLastError();
+}
+
+// single block: per-row log-sum-exp, loss, dlogits
+__global__ __launch_bounds__(kThreads) void softmax_ce_kernel(const float* __restrict__ logits, const int32_t* __restrict__ labels,
+                                                              float* __restrict__ y, float* __restrict__ dl, int N, int J) {
+  __shared__ float red[kThreads];
+  float part = 0.f;
+  for (int n = threadIdx.x; n < N; n += kThreads) {
+    const float* l = logits + (size_t)n * J;
+    float mx = l[0];
+    for (int j = 1; j < J; ++j) mx = fmaxf(mx, l[j]);
+    float z = 0.f;
+    for (int j = 0; j < J; ++j) z += expf(l[j] - mx);
+    const float lse = mx + logf(z);
+    const int lab = min(max(labels[n], 0), J - 1);
+    part += lse - l[lab];
+    for (int j = 0; j < J; ++j) {
+      const float sm = expf(l[j] - lse);
+      dl[(size_t)n * J + j] = (sm - (j == lab ? 1.f : 0.f)) / (float)N;
+      y[1 + (size_t)n * J + j] = l[j];
+    }
+  }
+  red[threadIdx.x] = part;
+  __syncthreads();
+  for (int off = kThreads / 2; off > 0; off >>= 1) {
+    if (threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) y[0] = red[0] / (float)N;
+}
+hipError_t launch_softmax_ce(const float* logits, const int32_t* labels, float* y, float* dl, int N, int J,
+                             hipStream_t s) {
+  hipLaunchKernelGGL(softmax_ce_kernel, dim3(1), dim3(kThreads), 0, s, logits, labels, y, dl, N, J);
+  return hipGetLastError();
+}
+
+// dW[j,c] = sum_n dl[n,j] p[n,c];  db[j] = sum_n dl[n,j];  dp[n,c] = sum_j dl[n,j] W[j,c]
+__global__ void fc_bwd_kernel(const float* __restrict__ pooled, const float* __restrict__ W, const float* __restrict__ dl,
+                              float* __restrict__ dW, float* __restrict__ db, float* __restrict__ dp, int N, int C, int J) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < J * C) {
+    const int j = idx / C, c = idx % C;
+    float s = 0.f;
+    for (int n = 0; n < N; ++n) s += dl[(size_t)n * J + j] * pooled[(size_t)n * C + c];
+    dW[idx] = s;
+  }
+  if (idx < J) {
+    float s = 0.f;
+    for (int n = 0; n < N; ++n) s += dl[(size_t)n * J + idx];
+    db[idx] = s;
+  }
+  if (idx < N * C) {
+    const int n = idx / C, c = idx % C;
+    float s = 0.f;
+    for (int j = 0; j < J; ++j) s += dl[(size_t)n * J + j] * W[(size_t)j * C + c];
+    dp[idx] = s;
+  }
+}
+hipError_t launch_fc_bwd(const float* pooled, const float* W, const float* dl, float* dW, float* db, float* dp,
+                         int N, int C, int J, hipStream_t s) {
+  const int total = (N > J ? N : J) * C;
+  hipLaunchKernelGGL(fc_bwd_kernel, dim3((total + 255) / 256), dim3(256), 0, s, pooled, W, dl, dW, db, dp, N, C, J);
+  return hipGetLastError();
+}
+
+__global__ void pool_bwd_kernel(const float* __restrict__ dp, float* __restrict__ g_f32, bf16_t* __restrict__ g_b16, int N,
+                                int HW, int C) {
+  const size_t total = (size_t)N * HW * C;
+  const float inv = 1.f / (float)HW;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const int c = (int)(i % C);
+    const int n = (int)(i / ((size_t)HW * C));
+    const float v = dp[(size_t)n * C + c] * inv;
+    if (g_f32) g_f32[i] = v;
+    if (g_b16) g_b16[i] = (bf16_t)v;
+  }
+}
+hipError_t launch_pool_bwd(const float* dp, float* g_f32, bf16_t* g_b16, int N, int HW, int C, hipStream_t s) {
+  hipLaunchKernelGGL(pool_bwd_kernel, dim3(stream_grid((size_t)N * HW * C)), dim3(256), 0, s, dp, g_f32, g_b16, N, HW, C);
+  return hipGetLastError();
+}
+
+// ---- momentum SGD (Eq. 11 with the optimiser of Section V-A) ------------------------------------------
+__global__ __launch_bounds__(kThreads) void sgd_kernel(float4* __restrict__ theta, float4* __restrict__ v,
+                                                       const float4* __restrict__ g, size_t n4, float lr, float mu, float wd) {
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += (size_t)gridDim.x * kThreads) {
+    float4 t = theta[i], m = v[i];
+    const float4 gg = g[i];
+    m.x = mu * m.x + (gg.x + wd * t.x);
+    m.y = mu * m.y + (gg.y + wd * t.y);
+    m.z = mu * m.z + (gg.z + wd * t.z);
+    m.w = mu * m.w + (gg.w + wd * t.w);
+    t.x -= lr * m.x;
+    t.y -= lr * m.y;
+    t.z -= lr * m.z;
+    t.w -= lr * m.w;
+    v[i] = m;
+    theta[i] = t;
+  }
+}
+hipError_t launch_sgd(float* theta, float* v, const float* g, size_t count, float lr, float mu, float wd, hipStream_t s) {
+  if (count % 4 != 0) return hipErrorInvalidValue;
+  if (count == 0) return hipSuccess;
+  const size_t n4 = count / 4;
+  size_t blocks = (n4 + kThreads - 1) / kThreads;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(sgd_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, s, reinterpret_cast<float4*>(theta),
+                     reinterpret_cast<float4*>(v), reinterpret_cast<const float4*>(g), n4, lr, mu, wd);
+  return hipGetLastError();
+}
+
+// ---- bf16 weight snapshot ------------------------------------------------------------------------
+// One block handles 1024 consecutive elements of one convolution's padded [Co][T][Cip] layout.
+__global__ __launch_bounds__(kThreads) void emit_weights_kernel(const float* __restrict__ params, bf16_t* __restrict__ warena,
+                                                                const WeightEmitEntry* __restrict__ table, int nconv) {
+  // find the conv this block belongs to (block_start is ascending)
+  int lo = 0, hi = nconv - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (table[mid].block_start <= blockIdx.x) lo = mid; else hi = mid - 1;
+  }
+  const WeightEmitEntry e = table[lo];
+  const int per_co = e.T * e.Cip;
+  const int total = e.Co * per_co;
+  const int base = (blockIdx.x - e.block_start) * 1024;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int idx = base + q * kThreads + threadIdx.x;
+    if (idx >= total) break;
+    const int co = idx / per_co, rem = idx % per_co, t = rem / e.Cip, ci = rem % e.Cip;
+    const float v = ci < e.Ci ? params[e.src_off + ((size_t)co * e.T + t) * e.Ci + ci] : 0.f;
+    const bf16_t b = (bf16_t)v;
+    warena[e.w_off + idx] = b;
+    warena[e.wt_off + ((size_t)ci * e.T + t) * e.Co + co] = b;
+  }
+}
+hipError_t launch_emit_weights(const float* params, bf16_t* warena, const WeightEmitEntry* table_dev, int nconv,
+                               int total_blocks, hipStream_t s) {
+  if (nconv <= 0) return hipSuccess;
+  hipLaunchKernelGGL(emit_weights_kernel, dim3(total_blocks), dim3(kThreads), 0, s, params, warena, table_dev, nconv);
+  return hipGetLastError();
+}
+
+// ---- fills ------------------------------------------------------------------------------------------
+__global__ void fill_zero_kernel(uint4* p, size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+    p[i] = make_uint4(0, 0, 0, 0);
+}
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+  if (bytes % 16 != 0) return hipErrorInvalidValue;
+  if (bytes == 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(stream_grid(bytes / 16)), dim3(256), 0, s, reinterpret_cast<uint4*>(p), bytes / 16);
+  return hipGetLastError();
+}
+__global__ void fill_f32_kernel(float* p, size_t n, float v) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+hipError_t launch_fill_f32(float* p, size_t count, float v, hipStream_t s) {
+  if (count == 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_f32_kernel, dim3(stream_grid(count)), dim3(256), 0, s, p, count, v);
+  return hipGetLastError();
+}
+
+}  // namespace fdg

@@ -1,0 +1,69 @@
+"""Marshalling for the per-kernel C entry points of include/fdg_kernels.h (same names).  Arguments are
+torch CUDA tensors (bf16 tensors for the *_b16 buffers) or None; nothing is computed here."""
+from __future__ import annotations
+
+import ctypes
+
+from .binding import _ptr, _stream_handle, load
+
+KERNEL_EXPORTS = ["fdgk_conv_fwd", "fdgk_conv_dgrad", "fdgk_conv_wgrad", "fdgk_bn_stats", "fdgk_bn_apply",
+                  "fdgk_bn_bwd", "fdgk_sgd"]
+_ready = False
+
+
+def _lib():
+    global _ready
+    lib = load()
+    if not _ready:
+        vp, i, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+        lib.fdgk_conv_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
+        lib.fdgk_conv_dgrad.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
+        lib.fdgk_conv_wgrad.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, vp]
+        lib.fdgk_bn_stats.argtypes = [vp, vp, i, i, vp]
+        lib.fdgk_bn_apply.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, f, i, vp]
+        lib.fdgk_bn_bwd.argtypes = [vp, i, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, f, vp]
+        lib.fdgk_sgd.argtypes = [vp, vp, vp, sz, f, f, f, vp]
+        for n in KERNEL_EXPORTS:
+            getattr(lib, n).restype = i
+        _ready = True
+    return lib
+
+
+def _ok(rc: int, name: str) -> None:
+    if rc != 0:
+        raise RuntimeError(f"{name} failed with hipError_t {rc}")
+
+
+def fdgk_conv_fwd(x_b16, w_b16, addend_f32, y_f32, y_b16, n, h, w, ci, co, ksize, stride, stream=None):
+    _ok(_lib().fdgk_conv_fwd(_ptr(x_b16), _ptr(w_b16), _ptr(addend_f32), _ptr(y_f32), _ptr(y_b16), n, h, w, ci, co,
+                             ksize, stride, _stream_handle(stream)), "fdgk_conv_fwd")
+
+
+def fdgk_conv_dgrad(dy_b16, wt_b16, addend_f32, addmask_b16, dx_f32, dx_b16, n, h, w, ci, co, ksize, stride, stream=None):
+    _ok(_lib().fdgk_conv_dgrad(_ptr(dy_b16), _ptr(wt_b16), _ptr(addend_f32), _ptr(addmask_b16), _ptr(dx_f32),
+                               _ptr(dx_b16), n, h, w, ci, co, ksize, stride, _stream_handle(stream)), "fdgk_conv_dgrad")
+
+
+def fdgk_conv_wgrad(x_b16, dy_b16, dw_f32, n, h, w, ci, co, ksize, stride, stream=None):
+    _ok(_lib().fdgk_conv_wgrad(_ptr(x_b16), _ptr(dy_b16), _ptr(dw_f32), n, h, w, ci, co, ksize, stride,
+                               _stream_handle(stream)), "fdgk_conv_wgrad")
+
+
+def fdgk_bn_stats(x_b16, sums_f32, m, c, stream=None):
+    _ok(_lib().fdgk_bn_stats(_ptr(x_b16), _ptr(sums_f32), m, c, _stream_handle(stream)), "fdgk_bn_stats")
+
+
+def fdgk_bn_apply(x_b16, sums_f32, gamma, beta, res_f32, y_f32, y_b16, m, c, eps, relu, stream=None):
+    _ok(_lib().fdgk_bn_apply(_ptr(x_b16), _ptr(sums_f32), _ptr(gamma), _ptr(beta), _ptr(res_f32), _ptr(y_f32),
+                             _ptr(y_b16), m, c, eps, int(relu), _stream_handle(stream)), "fdgk_bn_apply")
+
+
+def fdgk_bn_bwd(dy, dy_is_f32, mask_b16, x_b16, sums_f32, gamma, scratch_f32, addend_f32, dx_f32, dx_b16, dgamma,
+                dbeta, m, c, eps, stream=None):
+    _ok(_lib().fdgk_bn_bwd(_ptr(dy), int(dy_is_f32), _ptr(mask_b16), _ptr(x_b16), _ptr(sums_f32), _ptr(gamma),
+                           _ptr(scratch_f32), _ptr(addend_f32), _ptr(dx_f32), _ptr(dx_b16), _ptr(dgamma), _ptr(dbeta),
+                           m, c, eps, _stream_handle(stream)), "fdgk_bn_bwd")
+
+
+def fdgk_sgd(theta, v, g, count, lr, mu, wd, stream=None):
+    _ok(_lib().fdgk_sgd(_ptr(theta), _ptr(v), _ptr(g), count, lr, mu, wd, _stream_handle(stream)), "fdgk_sgd")

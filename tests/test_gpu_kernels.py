@@ -1,0 +1,218 @@
+"""Per-kernel GPU parity against the oracle's layer loops.  Inputs are rounded to bf16 first and the
+oracle receives exactly those values, so only accumulation order and output rounding differ:
+fp32 outputs must agree to 2e-4 of the tensor's largest magnitude, bf16 outputs to 2^-8."""
+import numpy as np
+import pytest
+
+from oracle.fdg_oracle import Kernels
+
+pytestmark = pytest.mark.gpu
+
+F32_TOL = 2e-4
+B16_TOL = 2.0 ** -8
+K32 = Kernels(np.float32)
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def bf16_round(a: np.ndarray) -> np.ndarray:
+    t = _torch()
+    return t.from_numpy(np.ascontiguousarray(a, np.float32)).to(t.bfloat16).to(t.float32).numpy()
+
+
+def to_dev_nhwc_b16(a_nchw: np.ndarray, cpad: int = 0):
+    """NCHW fp32 (already bf16-representable) -> device NHWC bf16, channels zero-padded to cpad."""
+    t = _torch()
+    x = t.from_numpy(np.ascontiguousarray(a_nchw.transpose(0, 2, 3, 1)))
+    if cpad and cpad > x.shape[3]:
+        x = t.nn.functional.pad(x, (0, cpad - x.shape[3]))
+    return x.to(t.bfloat16).contiguous().cuda()
+
+
+def to_dev_nhwc_f32(a_nchw: np.ndarray):
+    t = _torch()
+    return t.from_numpy(np.ascontiguousarray(a_nchw.transpose(0, 2, 3, 1))).contiguous().cuda()
+
+
+def nhwc_to_nchw(tns) -> np.ndarray:
+    t = _torch()
+    return tns.to(t.float32).cpu().numpy().transpose(0, 3, 1, 2)
+
+
+def rel(got, ref):
+    d = np.abs(ref).max()
+    return float(np.abs(np.asarray(got, np.float64) - ref).max() / (d if d > 0 else 1.0))
+
+
+CONV_CASES = [  # n, h, w, ci, co, ksize, stride
+    (3, 7, 5, 16, 16, 3, 1),
+    (2, 8, 8, 16, 32, 3, 2),
+    (2, 9, 7, 8, 24, 3, 2),
+    (2, 6, 6, 96, 160, 3, 1),
+    (4, 8, 8, 32, 32, 1, 2),
+    (3, 7, 7, 16, 40, 1, 2),
+    (2, 5, 5, 24, 16, 1, 1),
+    (2, 6, 5, 3, 16, 3, 1),
+    (2, 16, 16, 64, 64, 3, 1),
+    (8, 8, 8, 320, 320, 3, 1),
+    (4, 16, 16, 160, 320, 3, 2),
+    (16, 32, 32, 16, 16, 3, 1),
+]
+
+
+def _conv_data(case, seed):
+    n, h, w, ci, co, k, s = case
+    r = np.random.default_rng(seed)
+    x = bf16_round(r.standard_normal((n, ci, h, w)))
+    wt = bf16_round(r.standard_normal((co, ci, k, k)) * np.sqrt(2.0 / (ci * k * k)))
+    ho, wo = (h - 1) // s + 1, (w - 1) // s + 1
+    dy = bf16_round(r.standard_normal((n, co, ho, wo)))
+    return x, wt, dy, ho, wo
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_fwd(case):
+    from paper_1906_09108_amd import kernels as K
+    t = _torch()
+    n, h, w, ci, co, k, s = case
+    print("conv_fwd", case, flush=True)
+    x, wt, _, ho, wo = _conv_data(case, 1)
+    cip = (ci + 7) // 8 * 8
+    ref = K32.conv_fwd(x, wt, s, 1 if k == 3 else 0).astype(np.float64)
+    xd = to_dev_nhwc_b16(x, cip)
+    wd = t.nn.functional.pad(t.from_numpy(wt.transpose(0, 2, 3, 1).copy()), (0, cip - ci)).to(t.bfloat16).contiguous().cuda()
+    add = np.random.default_rng(2).standard_normal(ref.shape).astype(np.float32)
+    y32 = t.full((n, ho, wo, co), float("nan"), dtype=t.float32, device="cuda")
+    y16 = t.zeros((n, ho, wo, co), dtype=t.bfloat16, device="cuda")
+    K.fdgk_conv_fwd(xd, wd, None, y32, y16, n, h, w, ci, co, k, s)
+    t.cuda.synchronize()
+    assert rel(nhwc_to_nchw(y32), ref) <= F32_TOL
+    assert rel(nhwc_to_nchw(y16), ref) <= B16_TOL
+    K.fdgk_conv_fwd(xd, wd, to_dev_nhwc_f32(add), y32, None, n, h, w, ci, co, k, s)
+    t.cuda.synchronize()
+    assert rel(nhwc_to_nchw(y32), ref + add) <= F32_TOL
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_dgrad(case):
+    from paper_1906_09108_amd import kernels as K
+    t = _torch()
+    n, h, w, ci, co, k, s = case
+    print("conv_dgrad", case, flush=True)
+    x, wt, dy, ho, wo = _conv_data(case, 3)
+    cip = (ci + 7) // 8 * 8
+    ref = K32.conv_bwd_data(dy, wt, x.shape, s, 1 if k == 3 else 0).astype(np.float64)
+    dyd = to_dev_nhwc_b16(dy)
+    # [cip][k*k][co]
+    wtd = t.nn.functional.pad(t.from_numpy(wt.transpose(1, 2, 3, 0).copy()), (0, 0, 0, 0, 0, 0, 0, cip - ci))
+    wtd = wtd.to(t.bfloat16).contiguous().cuda()
+    dx32 = t.full((n, h, w, cip), float("nan"), dtype=t.float32, device="cuda")
+    dx16 = t.zeros((n, h, w, cip), dtype=t.bfloat16, device="cuda")
+    K.fdgk_conv_dgrad(dyd, wtd, None, None, dx32, dx16, n, h, w, ci, co, k, s)
+    t.cuda.synchronize()
+    got = nhwc_to_nchw(dx32)
+    assert rel(got[:, :ci], ref) <= F32_TOL
+    assert np.all(got[:, ci:] == 0)
+    assert rel(nhwc_to_nchw(dx16)[:, :ci], ref) <= B16_TOL
+    # masked addend (the identity shortcut through a ReLU)
+    r = np.random.default_rng(4)
+    add = r.standard_normal((n, cip, h, w)).astype(np.float32)
+    mask = bf16_round(np.maximum(r.standard_normal((n, cip, h, w)), 0))
+    K.fdgk_conv_dgrad(dyd, wtd, to_dev_nhwc_f32(add), to_dev_nhwc_b16(mask), dx32, None, n, h, w, ci, co, k, s)
+    t.cuda.synchronize()
+    full = np.zeros((n, cip, h, w))
+    full[:, :ci] = ref
+    assert rel(nhwc_to_nchw(dx32), full + add * (mask > 0)) <= F32_TOL
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_wgrad(case):
+    from paper_1906_09108_amd import kernels as K
+    t = _torch()
+    n, h, w, ci, co, k, s = case
+    print("conv_wgrad", case, flush=True)
+    x, wt, dy, ho, wo = _conv_data(case, 5)
+    cip = (ci + 7) // 8 * 8
+    ref = K32.conv_bwd_weight(x, dy, k, s, 1 if k == 3 else 0).astype(np.float64)   # [co, ci, k, k]
+    dw = t.zeros((co, k * k, ci), dtype=t.float32, device="cuda")
+    K.fdgk_conv_wgrad(to_dev_nhwc_b16(x, cip), to_dev_nhwc_b16(dy), dw, n, h, w, ci, co, k, s)
+    t.cuda.synchronize()
+    got = dw.cpu().numpy().reshape(co, k, k, ci).transpose(0, 3, 1, 2)
+    assert rel(got, ref) <= F32_TOL
+
+
+BN_CASES = [(189, 16), (4096, 16), (1000, 40), (512, 640), (16384, 32), (77, 2048)]
+
+
+@pytest.mark.parametrize("m,c", BN_CASES)
+def test_bn_forward_and_backward(m, c):
+    from paper_1906_09108_amd import kernels as K
+    t = _torch()
+    print("bn", m, c, flush=True)
+    r = np.random.default_rng(m + c)
+    eps = 1e-5
+    x = bf16_round(r.standard_normal((m, c)) * (0.5 + r.random(c)) + r.standard_normal(c))
+    gamma = (1 + 0.2 * r.standard_normal(c)).astype(np.float32)
+    beta = (0.2 * r.standard_normal(c)).astype(np.float32)
+    res = r.standard_normal((m, c)).astype(np.float32)
+    x4 = x.T.reshape(1, c, m, 1)                      # oracle layout: N=1, C, H=m, W=1
+    y_ref, mean, var, invstd = K32.bn_fwd(x4, gamma, beta, eps)
+    xd = t.from_numpy(x).to(t.bfloat16).cuda()
+    sums = t.zeros(2 * c, dtype=t.float32, device="cuda")
+    K.fdgk_bn_stats(xd, sums, m, c)
+    t.cuda.synchronize()
+    s = sums.cpu().numpy()
+    assert rel(s[:c] / m, mean.astype(np.float64)) <= 1e-5
+    assert rel(s[c:] / m - (s[:c] / m) ** 2, var.astype(np.float64)) <= 1e-4
+    gd, bd = t.from_numpy(gamma).cuda(), t.from_numpy(beta).cuda()
+    y32 = t.empty((m, c), dtype=t.float32, device="cuda")
+    y16 = t.empty((m, c), dtype=t.bfloat16, device="cuda")
+    K.fdgk_bn_apply(xd, sums, gd, bd, None, y32, y16, m, c, eps, 0)
+    t.cuda.synchronize()
+    ref2d = y_ref.reshape(c, m).T.astype(np.float64)
+    assert rel(y32.cpu().numpy(), ref2d) <= F32_TOL
+    K.fdgk_bn_apply(xd, sums, gd, bd, t.from_numpy(res).cuda(), y32, y16, m, c, eps, 1)
+    t.cuda.synchronize()
+    out_ref = np.maximum(ref2d + res, 0)
+    assert rel(y32.cpu().numpy(), out_ref) <= F32_TOL
+    assert rel(y16.to(t.float32).cpu().numpy(), out_ref) <= B16_TOL
+    # backward through the ReLU gate and the normalisation, for both gradient storage types
+    mask = y16                                         # gate = ReLU output > 0, as the module uses it
+    gate = (mask.to(t.float32).cpu().numpy() > 0)
+    for dy_is_f32 in (True, False):
+        dy = r.standard_normal((m, c)).astype(np.float32)
+        if not dy_is_f32:
+            dy = bf16_round(dy)
+        g = (dy * gate).astype(np.float32)
+        dx_ref, dgamma_ref, dbeta_ref = K32.bn_bwd(x4, g.T.reshape(1, c, m, 1), gamma, mean, invstd)
+        add = r.standard_normal((m, c)).astype(np.float32)
+        dyd = t.from_numpy(dy).cuda() if dy_is_f32 else t.from_numpy(dy).to(t.bfloat16).cuda()
+        scratch = t.zeros(2 * c, dtype=t.float32, device="cuda")
+        dx32 = t.empty((m, c), dtype=t.float32, device="cuda")
+        dx16 = t.empty((m, c), dtype=t.bfloat16, device="cuda")
+        dg, db = t.empty(c, dtype=t.float32, device="cuda"), t.empty(c, dtype=t.float32, device="cuda")
+        K.fdgk_bn_bwd(dyd, dy_is_f32, mask, xd, sums, gd, scratch, t.from_numpy(add).cuda(), dx32, dx16, dg, db, m, c, eps)
+        t.cuda.synchronize()
+        assert rel(db.cpu().numpy(), dbeta_ref.astype(np.float64)) <= F32_TOL
+        assert rel(dg.cpu().numpy(), dgamma_ref.astype(np.float64)) <= F32_TOL
+        dref = dx_ref.reshape(c, m).T.astype(np.float64) + add
+        assert rel(dx32.cpu().numpy(), dref) <= F32_TOL
+        assert rel(dx16.to(t.float32).cpu().numpy(), dref) <= B16_TOL
+
+
+@pytest.mark.parametrize("count", [4, 1024, 4672, 1 << 20])
+def test_sgd(count):
+    from paper_1906_09108_amd import kernels as K
+    t = _torch()
+    r = np.random.default_rng(count)
+    theta, v, g = (r.standard_normal(count).astype(np.float32) for _ in range(3))
+    td, vd, gd = (t.from_numpy(a.copy()).cuda() for a in (theta, v, g))
+    for _ in range(3):
+        K32.sgd_momentum(theta, v, g, 0.1, 0.9, 5e-4)
+        K.fdgk_sgd(td, vd, gd, count, 0.1, 0.9, 5e-4)
+    t.cuda.synchronize()
+    assert rel(td.cpu().numpy(), theta.astype(np.float64)) <= 1e-6
+    assert rel(vd.cpu().numpy(), v.astype(np.float64)) <= 1e-6

@@ -1,0 +1,67 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares, and its
+host logic (descriptor validation, workspace sizing) behaves; no kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import fdg_workloads as W
+from fdg_workloads import Layer, ModuleSpec
+from paper_1906_09108_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared(header, prefix):
+    text = open(os.path.join(ROOT, "include", header)).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(" + prefix + r"[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_1906_09108_amd import kernels
+    lib = binding.load()
+    names = _declared("fdg.h", "fdg_")
+    assert set(names) == set(binding.EXPORTS)
+    knames = _declared("fdg_kernels.h", "fdgk_")
+    assert set(knames) == set(kernels.KERNEL_EXPORTS)
+    for n in names + knames:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings():
+    lib = binding.load()
+    assert lib.fdg_status_string(0) == b"ok"
+    assert b"queue" in lib.fdg_status_string(4)
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+def test_workspace_bytes_of_benchmark_configs(idx):
+    spec = W.config(idx)
+    b = binding.fdg_module_workspace_bytes(spec)
+    assert b > 0 and b % 256 == 0
+    deeper = W.config(idx)
+    deeper.delay += 1
+    assert binding.fdg_module_workspace_bytes(deeper) > b      # one more ring slot
+
+
+def test_invalid_descriptors_are_rejected():
+    ok = ModuleSpec(2, 16, 8, 8, [Layer(W.BASIC_POSTACT, 16, 16, 1)])
+    assert binding.fdg_module_workspace_bytes(ok) > 0
+    for bad in (ModuleSpec(2, 16, 8, 8, [Layer(W.BASIC_POSTACT, 8, 16, 1)]),          # channel mismatch
+                ModuleSpec(2, 16, 8, 8, [Layer(W.BASIC_POSTACT, 16, 16, 3)]),         # stride
+                ModuleSpec(2, 16, 8, 8, [Layer(W.BASIC_POSTACT, 16, 16, 1)], beta=0.0),
+                ModuleSpec(2, 16, 8, 8, [Layer(W.BASIC_POSTACT, 16, 16, 1)], delay=-1),
+                ModuleSpec(2, 16, 8, 8, [Layer(W.HEAD_POSTACT, 16), Layer(W.BASIC_POSTACT, 16, 16, 1)]),  # head not last
+                ModuleSpec(2, 16, 8, 8, [Layer(W.BASIC_POSTACT, 16, 12, 1)]),         # channels not a multiple of 8
+                ModuleSpec(0, 16, 8, 8, [Layer(W.BASIC_POSTACT, 16, 16, 1)])):
+        assert binding.fdg_module_workspace_bytes(bad) == 0
+    lib = binding.load()
+    assert lib.fdg_module_workspace_bytes(None) == 0
+    out = ctypes.c_void_p()
+    d, keep = binding.make_desc(ok)
+    assert lib.fdg_module_create(ctypes.byref(d), None, 0, None, ctypes.byref(out)) == binding.FDG_ERR_INVALID_ARG
+    assert lib.fdg_forward(None, None, None, None, None) == binding.FDG_ERR_INVALID_ARG
+    assert lib.fdg_update(None, 0.1, None) == binding.FDG_ERR_INVALID_ARG
+    lib.fdg_destroy(None)
