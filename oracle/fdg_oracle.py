@@ -29,6 +29,18 @@ Readings taken where the paper is silent (all listed in the design notes of the 
   * BN: eps inside the square root, biased batch variance for normalising, running statistics
     updated with the unbiased variance; no convolution bias; loss = mean softmax cross-entropy.
 
+Two storage precisions.  storage="fp32" is the plain definition above.  storage="bf16" evaluates the
+SAME steps but rounds a tensor to bfloat16 (fdgref_round_bf16: nearest, ties to even) at exactly the
+points where the bf16 matrix-core path stores one: the convolution weights as used by a forward, every
+convolution / BN+ReLU output that is kept, the bf16 copy of a block's input and output, and the
+gradients handed to a convolution.  Residual sums, BN statistics, parameter gradients and the
+optimiser stay in the oracle's full precision.  The mode exists because ReLU turns a float into a
+decision (gradient passes or not): compared with the fp32 definition, a path with bf16 operands
+decides differently for about 4 in 10^4 activations, and with noise gradients every such element
+moves a per-channel sum by a whole term, which alone puts parameter gradients several per cent away.
+Taking the decision in the kernel's storage precision on both sides removes that, and what remains
+is the arithmetic.
+
 Parity status: every function of this oracle is pinned by tests/test_oracle_*.py (finite
 differences in float64, torch-CPU autograd as an independent library, closed forms, adjoint
 identities, brute force, and the paper's own K=3 delay example).  Nothing here is "parity unpinned".
@@ -193,6 +205,12 @@ class Kernels:
         loss = self.lib.fdgref_softmax_ce(_p(logits), _p(labels), _p(dl), N, J)
         return float(loss), dl
 
+    def round_bf16(self, x) -> np.ndarray:
+        """A copy of x with every element rounded to the nearest bfloat16 (ties to even)."""
+        y = np.array(x, dtype=self.dt, order="C", copy=True)
+        self.lib.fdgref_round_bf16(_p(y), ctypes.c_size_t(y.size))
+        return y
+
     def sgd_momentum(self, theta, v, g, lr: float, mu: float, wd: float) -> None:
         """In place on theta and v."""
         assert theta.dtype == self.dt and v.dtype == self.dt and g.dtype == self.dt
@@ -271,10 +289,12 @@ class OracleModule:
     descriptor (n, c_in, h_in, w_in, layers[kind,c_in,c_out,stride], delay, is_bottom, num_classes,
     beta, momentum, weight_decay, bn_eps, bn_momentum)."""
 
-    def __init__(self, spec, dtype=np.float32):
+    def __init__(self, spec, dtype=np.float32, storage: str = "fp32"):
+        assert storage in ("fp32", "bf16")
         self.spec = spec
         self.dt = np.dtype(dtype)
         self.k = Kernels(dtype)
+        self.storage = storage
         self.layout = oracle_param_layout(spec)
         self.theta = _Flat(self.layout, self.dt)
         self.v = np.zeros_like(self.theta.flat)
@@ -335,60 +355,75 @@ class OracleModule:
         g[key + ".beta"][...] = dbeta
         return dx
 
+    # ---- storage precision ------------------------------------------------------------------------
+    def _q(self, x):
+        """Identity in fp32 storage; rounds to bfloat16 where the bf16 path stores bfloat16."""
+        return self.k.round_bf16(x) if self.storage == "bf16" else x
+
+    def _stored_weights(self, theta: _Flat) -> _Flat:
+        """The parameters as a forward uses them: convolution weights in storage precision."""
+        if self.storage != "bf16":
+            return theta
+        th = theta.copy()
+        for name, shape in self.layout:
+            if len(shape) == 4:
+                th[name][...] = self.k.round_bf16(th[name])
+        return th
+
     # ---- forward -------------------------------------------------------------------------------
     def forward(self, x, labels=None):
-        """Section III-A forward step.  Returns the module output (top module: [loss, logits...])."""
+        """Section III-A forward step.  Returns the module output (top module: [loss, logits...]).
+        z is the residual stream in full precision, zb its stored copy (conv / BN operand)."""
         if len(self.fifo) >= self.spec.delay + 1:
             raise QueueFull()
-        k = self.k
-        th = self.theta.copy()          # parameters of THIS iteration, kept for the delayed backward
+        k, q = self.k, self._q
+        th = self._stored_weights(self.theta.copy())   # parameters of THIS iteration, kept for the backward
         tapes: List[dict] = []
         z = np.ascontiguousarray(x, dtype=self.dt)
         assert z.shape == (self.spec.n, self.spec.c_in, self.spec.h_in, self.spec.w_in)
+        zb = q(z)
         out = None
         for i, L in enumerate(self.spec.layers):
-            t: dict = {"x": z}
+            t: dict = {"x": zb}
             if L.kind == STEM:
-                c = k.conv_fwd(z, th[f"{i}.conv.w"], L.stride, 1)
+                c = q(k.conv_fwd(zb, th[f"{i}.conv.w"], L.stride, 1))
                 b = self._bn(f"{i}.bn", c, th, t)
-                t["b"] = b
                 z = k.relu_fwd(b)
             elif L.kind == BASIC_POSTACT:
-                c1 = k.conv_fwd(z, th[f"{i}.conv1.w"], L.stride, 1)
-                b1 = self._bn(f"{i}.bn1", c1, th, t)
-                a1 = k.relu_fwd(b1)
-                c2 = k.conv_fwd(a1, th[f"{i}.conv2.w"], 1, 1)
+                c1 = q(k.conv_fwd(zb, th[f"{i}.conv1.w"], L.stride, 1))
+                a1 = q(k.relu_fwd(self._bn(f"{i}.bn1", c1, th, t)))
+                c2 = q(k.conv_fwd(a1, th[f"{i}.conv2.w"], 1, 1))
                 b2 = self._bn(f"{i}.bn2", c2, th, t)
                 if _projects(L):
-                    sc = self._bn(f"{i}.bnp", k.conv_fwd(z, th[f"{i}.proj.w"], L.stride, 0), th, t)
+                    sc = self._bn(f"{i}.bnp", q(k.conv_fwd(zb, th[f"{i}.proj.w"], L.stride, 0)), th, t)
                 else:
                     sc = z
-                s = b2 + sc
-                t.update(b1=b1, a1=a1, s=s)
-                z = k.relu_fwd(s)
+                t.update(a1=a1)
+                z = k.relu_fwd(b2 + sc)
             elif L.kind == BASIC_PREACT:
-                b1 = self._bn(f"{i}.bn1", z, th, t)
-                o1 = k.relu_fwd(b1)
-                c1 = k.conv_fwd(o1, th[f"{i}.conv1.w"], L.stride, 1)
-                b2 = self._bn(f"{i}.bn2", c1, th, t)
-                o2 = k.relu_fwd(b2)
+                o1 = q(k.relu_fwd(self._bn(f"{i}.bn1", zb, th, t)))
+                c1 = q(k.conv_fwd(o1, th[f"{i}.conv1.w"], L.stride, 1))
+                o2 = q(k.relu_fwd(self._bn(f"{i}.bn2", c1, th, t)))
                 c2 = k.conv_fwd(o2, th[f"{i}.conv2.w"], 1, 1)
                 sc = k.conv_fwd(o1, th[f"{i}.proj.w"], L.stride, 0) if _projects(L) else z
-                t.update(b1=b1, o1=o1, b2=b2, o2=o2)
+                t.update(o1=o1, o2=o2)
                 z = c2 + sc
             elif L.kind in (HEAD_POSTACT, HEAD_PREACT):
                 assert i == len(self.spec.layers) - 1 and labels is not None
                 if L.kind == HEAD_PREACT:
-                    b = self._bn(f"{i}.bn", z, th, t)
-                    t["b"] = b
-                    o = k.relu_fwd(b)
+                    o = q(k.relu_fwd(self._bn(f"{i}.bn", zb, th, t)))
+                    t["o"] = o
                 else:
-                    o = z
+                    o = zb
                 p = k.avgpool_fwd(o)
                 logits = k.fc_fwd(p, th[f"{i}.fc.w"], th[f"{i}.fc.b"])
                 loss, dl = k.softmax_ce(logits, labels)
                 t.update(o_shape=o.shape, p=p, dl=dl)
                 out = np.concatenate([np.array([loss], self.dt), logits.reshape(-1)])
+                tapes.append(t)
+                break
+            zb = q(z)
+            t["y"] = zb          # stored copy of the layer output: next operand and ReLU gate (y > 0)
             tapes.append(t)
         if out is None:
             out = z
@@ -399,13 +434,14 @@ class OracleModule:
     # ---- delayed backward ----------------------------------------------------------------------
     def backward_delayed(self, grad_out=None):
         """Eq. 10 with the shrinking of Eq. 15 on the oldest saved forward.  Returns the gradient of
-        the module input (None for a bottom module)."""
+        the module input (None for a bottom module).  A ReLU passes the gradient where its stored
+        output is positive, which is where its input was."""
         if not self.fifo:
             raise QueueEmpty()
         ctx = self.fifo.popleft()
         assert ctx["seq"] == self.seq_bwd
         self.seq_bwd += 1
-        k, th, tapes = self.k, ctx["theta"], ctx["tapes"]
+        k, q, th, tapes = self.k, self._q, ctx["theta"], ctx["tapes"]
         g = _Flat(self.layout, self.dt)
         if self.is_top:
             assert grad_out is None
@@ -423,25 +459,22 @@ class OracleModule:
                 g[f"{i}.fc.b"][...] = db
                 do = k.avgpool_bwd(dp, t["o_shape"])
                 if L.kind == HEAD_PREACT:
-                    db_ = k.relu_bwd(t["b"], do)
-                    dz = self._bn_back(f"{i}.bn", db_, th, t, g)
+                    dz = self._bn_back(f"{i}.bn", k.relu_bwd(t["o"], do), th, t, g)
                 else:
                     dz = do
             elif L.kind == STEM:
-                dbn = k.relu_bwd(t["b"], dz)
-                dc = self._bn_back(f"{i}.bn", dbn, th, t, g)
+                dc = q(self._bn_back(f"{i}.bn", k.relu_bwd(t["y"], dz), th, t, g))
                 g[f"{i}.conv.w"][...] = k.conv_bwd_weight(x, dc, 3, L.stride, 1)
                 dz = k.conv_bwd_data(dc, th[f"{i}.conv.w"], x.shape, L.stride, 1) if need_dx else None
             elif L.kind == BASIC_POSTACT:
-                ds = k.relu_bwd(t["s"], dz)                 # through the final ReLU; feeds both branches
-                dc2 = self._bn_back(f"{i}.bn2", ds, th, t, g)
+                ds = k.relu_bwd(t["y"], dz)                 # through the final ReLU; feeds both branches
+                dc2 = q(self._bn_back(f"{i}.bn2", ds, th, t, g))
                 g[f"{i}.conv2.w"][...] = k.conv_bwd_weight(t["a1"], dc2, 3, 1, 1)
-                da1 = k.conv_bwd_data(dc2, th[f"{i}.conv2.w"], t["a1"].shape, 1, 1)
-                db1 = k.relu_bwd(t["b1"], da1)
-                dc1 = self._bn_back(f"{i}.bn1", db1, th, t, g)
+                da1 = q(k.conv_bwd_data(dc2, th[f"{i}.conv2.w"], t["a1"].shape, 1, 1))
+                dc1 = q(self._bn_back(f"{i}.bn1", k.relu_bwd(t["a1"], da1), th, t, g))
                 g[f"{i}.conv1.w"][...] = k.conv_bwd_weight(x, dc1, 3, L.stride, 1)
                 if _projects(L):
-                    dpr = self._bn_back(f"{i}.bnp", ds, th, t, g)
+                    dpr = q(self._bn_back(f"{i}.bnp", ds, th, t, g))
                     g[f"{i}.proj.w"][...] = k.conv_bwd_weight(x, dpr, 1, L.stride, 0)
                 if need_dx:
                     dx = k.conv_bwd_data(dc1, th[f"{i}.conv1.w"], x.shape, L.stride, 1)
@@ -453,18 +486,18 @@ class OracleModule:
                 else:
                     dz = None
             elif L.kind == BASIC_PREACT:
-                # y = conv2(o2) + shortcut
-                g[f"{i}.conv2.w"][...] = k.conv_bwd_weight(t["o2"], dz, 3, 1, 1)
-                do2 = k.conv_bwd_data(dz, th[f"{i}.conv2.w"], t["o2"].shape, 1, 1)
-                db2 = k.relu_bwd(t["b2"], do2)
-                dc1 = self._bn_back(f"{i}.bn2", db2, th, t, g)
+                # y = conv2(o2) + shortcut; the convolutions take the stored copy of the gradient
+                dzb = q(dz)
+                g[f"{i}.conv2.w"][...] = k.conv_bwd_weight(t["o2"], dzb, 3, 1, 1)
+                do2 = q(k.conv_bwd_data(dzb, th[f"{i}.conv2.w"], t["o2"].shape, 1, 1))
+                dc1 = q(self._bn_back(f"{i}.bn2", k.relu_bwd(t["o2"], do2), th, t, g))
                 g[f"{i}.conv1.w"][...] = k.conv_bwd_weight(t["o1"], dc1, 3, L.stride, 1)
                 do1 = k.conv_bwd_data(dc1, th[f"{i}.conv1.w"], t["o1"].shape, L.stride, 1)
                 if _projects(L):
-                    g[f"{i}.proj.w"][...] = k.conv_bwd_weight(t["o1"], dz, 1, L.stride, 0)
-                    do1 = do1 + k.conv_bwd_data(dz, th[f"{i}.proj.w"], t["o1"].shape, L.stride, 0)
-                db1 = k.relu_bwd(t["b1"], do1)
-                dx = self._bn_back(f"{i}.bn1", db1, th, t, g)   # BN1 parameters need this even at the bottom
+                    g[f"{i}.proj.w"][...] = k.conv_bwd_weight(t["o1"], dzb, 1, L.stride, 0)
+                    do1 = do1 + k.conv_bwd_data(dzb, th[f"{i}.proj.w"], t["o1"].shape, L.stride, 0)
+                do1 = q(do1)
+                dx = self._bn_back(f"{i}.bn1", k.relu_bwd(t["o1"], do1), th, t, g)   # BN1 needs this even at the bottom
                 if not _projects(L):
                     dx = dx + dz
                 dz = dx if need_dx else None

@@ -278,4 +278,22 @@ void fdgref_sgd_momentum(real* theta, real* v, const real* g, size_t count, doub
   }
 }
 
+/* Round every element to the nearest bfloat16 (8 significand bits, ties to even) and store it back in
+ * `real`.  This is the storage precision of the MFMA operands and saved activations of the bf16 path;
+ * the oracle applies it only in its "bf16 storage" mode, at the points where that path stores bf16. */
+void fdgref_round_bf16(real* x, size_t count) {
+#pragma omp parallel for schedule(static)
+  for (size_t i = 0; i < count; ++i) {
+    float f = (float)x[i];
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    if ((u & 0x7f800000u) != 0x7f800000u) {          /* finite: add half an ulp of bf16, ties to even */
+      u += 0x7fffu + ((u >> 16) & 1u);
+      u &= 0xffff0000u;
+    }
+    memcpy(&f, &u, sizeof f);
+    x[i] = (real)f;
+  }
+}
+
 int fdgref_sizeof_real(void) { return (int)sizeof(real); }
