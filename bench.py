@@ -1,0 +1,154 @@
+#!/usr/bin/env python3
+"""Throughput of one FDG module step on one MI355X.
+
+A step is one pass of the whole hot path of a module worker: forward on the newest batch, delayed
+backward (with gradient shrinking) on the oldest saved batch, momentum-SGD update -- the three calls of
+the C ABI -- with the history ring in steady state and every input already resident in HBM.
+
+Prints ONE JSON line: images/s of the step, the roofline position of the kernel class that takes most of
+the step (timed with HIP events on the stream the kernels run on, during a second pass over the same
+steps), and the CPU oracle timed on this machine's host cores on a bounded sample (a reported baseline).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
+
+# algorithmic HBM traffic measured with rocprofv3 counters for the dominant kernel, per launch (bytes);
+# filled in from the committed summaries under profiles/ (None until measured)
+TRAFFIC_BYTES = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..5 (default 4: WRN-28-10 top module)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-batch", type=int, default=0, help="batch of the oracle sample (0 = pick by config)")
+    return ap.parse_args()
+
+
+def cpu_baseline(idx: int, sample_batch: int):
+    """The oracle as it stands (fp32 definition), one step of the same layers at a reduced batch."""
+    import numpy as np
+    import fdg_workloads as W
+    from oracle import fdg_oracle
+    n = sample_batch or {1: 16, 2: 16, 3: 32, 4: 8, 5: 8}[idx]
+    spec = W.config(idx, n=n)
+    spec.delay = 0
+    m = fdg_oracle.OracleModule(spec, np.float32, storage="fp32")
+    m.set_params(W.make_params(spec))
+    x, labels, g = W.make_input(spec, 0), W.make_labels(spec, 0), W.make_grad_out(spec, 0)
+    t0 = time.perf_counter()
+    m.forward(x, labels)
+    m.backward_delayed(g)
+    m.update(spec.lr)
+    dt = time.perf_counter() - t0
+    return {"value": n / dt, "unit": "images/s", "cores": fdg_oracle.num_threads(), "kind": "oracle",
+            "sample": f"same layers at batch {n} (of {W.config(idx).n}), 1 step forward+backward+update, {dt:.1f} s"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one module worker on ONE GPU; this build has no multi-GPU path "
+              f"(got --gpus {args.gpus}). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import fdg_workloads as W
+    from paper_1906_09108_amd import FdgModule
+
+    spec = W.config(args.config)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    mod = FdgModule(spec, dev)
+    mod.set_params(W.make_params(spec))
+
+    # a small pool of resident inputs, cycled, so consecutive steps do not re-read the same lines
+    pool = 4
+    xs = [torch.from_numpy(W.make_input(spec, t)).to(dev) for t in range(pool)]
+    labels = [None if not spec.is_top else torch.from_numpy(W.make_labels(spec, t)).to(dev) for t in range(pool)]
+    gs = [None if spec.is_top else torch.from_numpy(W.make_grad_out(spec, t)).to(dev) for t in range(pool)]
+    y = mod.new_output()
+    grad_in = None if spec.is_bottom else torch.empty(spec.input_shape(), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+    lr = 0.01   # small enough that the synthetic noise gradients do not blow the weights up over many steps
+
+    for t in range(spec.delay):                       # fill the history ring
+        mod.forward(xs[t % pool], labels[t % pool], y, stream)
+
+    def step(i):
+        mod.forward(xs[i % pool], labels[i % pool], y, stream)
+        mod.backward_delayed(gs[i % pool], grad_in, stream)
+        mod.update(lr, stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = spec.n * args.steps / elapsed
+    if not bool(torch.isfinite(y).all()):
+        print("non-finite module output", file=sys.stderr)
+        sys.exit(1)
+
+    # second pass over the same number of steps with per-class HIP events
+    mod.profile_enable(True)
+    for i in range(args.steps):
+        step(args.warmup + args.steps + i)
+    prof = mod.profile_read()
+    mod.profile_enable(False)
+    total_ms = sum(p["total_ms"] for p in prof.values())
+    name, dom = max(prof.items(), key=lambda kv: kv[1]["total_ms"])
+    avg_ms = dom["total_ms"] / dom["calls"]
+    if dom["flops"] > 0:
+        achieved = dom["flops"] / dom["calls"] / (avg_ms * 1e-3) / 1e12
+        roofline = {"kernel": name, "bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": achieved / PEAK_MFMA_BF16_TFLOPS}
+    else:
+        achieved = dom["bytes"] / dom["calls"] / (avg_ms * 1e-3) / 1e9
+        roofline = {"kernel": name, "bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": achieved / PEAK_HBM_GBS}
+    roofline.update({"avg_launch_ms": avg_ms, "calls_per_step": dom["calls"] / args.steps,
+                     "share_of_step": dom["total_ms"] / total_ms,
+                     "traffic": TRAFFIC_BYTES.get((args.config, name))})
+    classes = {k: {"ms_per_step": v["total_ms"] / args.steps, "calls_per_step": v["calls"] / args.steps,
+                   "TFLOP/s": (v["flops"] / (v["total_ms"] * 1e-3) / 1e12) if v["flops"] else None,
+                   "GB/s": v["bytes"] / (v["total_ms"] * 1e-3) / 1e9}
+               for k, v in sorted(prof.items(), key=lambda kv: -kv[1]["total_ms"])}
+    mod.close()
+
+    out = {
+        "metric": "images/sec per FDG module step (fwd+delayed bwd+update)",
+        "value": value, "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": spec.name, "batch": spec.n, "delay": spec.delay, "beta": spec.beta,
+                   "params": W.param_count(spec), "useful_conv_gflop_per_step": W.conv_flops(spec) / 1e9},
+        "step_tflops": W.conv_flops(spec) / (ms_per_step * 1e-3) / 1e12,
+        "roofline": roofline,
+        "kernel_classes": classes,
+        "paper_context": "FDG K=2 WRN-28-10: 354.56 images/s on 2x 1080Ti, BP 188.16 on 1x (Table VII); other hardware, whole system",
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.config, args.cpu_sample_batch)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

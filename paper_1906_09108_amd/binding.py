@@ -28,6 +28,11 @@ class fdg_layer_desc(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("c_in", ctypes.c_int32), ("c_out", ctypes.c_int32), ("stride", ctypes.c_int32)]
 
 
+class fdg_profile_entry(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char * 32), ("calls", ctypes.c_int64), ("total_ms", ctypes.c_double),
+                ("flops", ctypes.c_double), ("bytes", ctypes.c_double)]
+
+
 class fdg_module_desc(ctypes.Structure):
     _fields_ = [("n", ctypes.c_int32), ("c_in", ctypes.c_int32), ("h_in", ctypes.c_int32), ("w_in", ctypes.c_int32),
                 ("num_layers", ctypes.c_int32), ("layers", ctypes.POINTER(fdg_layer_desc)),
@@ -40,7 +45,8 @@ _lib: Optional[ctypes.CDLL] = None
 
 EXPORTS = ["fdg_module_workspace_bytes", "fdg_module_create", "fdg_forward", "fdg_backward_delayed", "fdg_update",
            "fdg_destroy", "fdg_param_count", "fdg_set_params", "fdg_get_params", "fdg_get_grads", "fdg_get_momentum",
-           "fdg_bn_stat_count", "fdg_get_bn_running", "fdg_output_shape", "fdg_queue_state", "fdg_status_string"]
+           "fdg_bn_stat_count", "fdg_get_bn_running", "fdg_output_shape", "fdg_queue_state", "fdg_status_string",
+           "fdg_profile_enable", "fdg_profile_read"]
 
 
 def load() -> ctypes.CDLL:
@@ -68,6 +74,9 @@ def load() -> ctypes.CDLL:
     lib.fdg_queue_state.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]
     lib.fdg_queue_state.restype = i32
     lib.fdg_status_string.argtypes, lib.fdg_status_string.restype = [i32], ctypes.c_char_p
+    lib.fdg_profile_enable.argtypes, lib.fdg_profile_enable.restype = [vp, i32], i32
+    lib.fdg_profile_read.argtypes = [vp, ctypes.POINTER(fdg_profile_entry), i32, ctypes.POINTER(i32)]
+    lib.fdg_profile_read.restype = i32
     _lib = lib
     return lib
 
@@ -220,6 +229,22 @@ class FdgModule:
 
     def get_bn_running(self):
         return self._get("fdg_get_bn_running", int(load().fdg_bn_stat_count(self.handle)))
+
+    def profile_enable(self, enable: bool) -> None:
+        st = load().fdg_profile_enable(self.handle, int(bool(enable)))
+        if st != FDG_OK:
+            raise FdgError(st, "fdg_profile_enable")
+
+    def profile_read(self) -> dict:
+        """{class name: dict(calls, total_ms, flops, bytes)} summed over the records since the enable."""
+        arr = (fdg_profile_entry * 16)()
+        n = ctypes.c_int32()
+        st = load().fdg_profile_read(self.handle, arr, 16, ctypes.byref(n))
+        if st != FDG_OK:
+            raise FdgError(st, "fdg_profile_read")
+        return {arr[i].name.decode(): dict(calls=int(arr[i].calls), total_ms=float(arr[i].total_ms),
+                                           flops=float(arr[i].flops), bytes=float(arr[i].bytes))
+                for i in range(min(n.value, 16))}
 
     def queue_state(self) -> Tuple[int, int, int]:
         o, a, b = ctypes.c_int32(), ctypes.c_int64(), ctypes.c_int64()

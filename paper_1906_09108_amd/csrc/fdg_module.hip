@@ -2,6 +2,7 @@
 // forwards, and the launch sequences of forward / delayed backward / update (Section III-A, Eq. 10,
 // Eq. 11 and Eq. 15 of arXiv 1906.09108).  This file holds no arithmetic: every number is produced
 // by the kernels in conv_kernels.hip and stream_kernels.hip.
+#include <cstdio>
 #include <new>
 #include <vector>
 
@@ -266,8 +267,33 @@ bool build_plan(const fdg_module_desc* desc, Plan& p, fdg_status* why) {
 
 }  // namespace
 
+// Optional per-kernel-class timing with HIP events on the stream the kernels run on.
+enum ProfClass { PC_CONV_FWD = 0, PC_CONV_DGRAD, PC_CONV_WGRAD, PC_BN_STATS, PC_BN_APPLY, PC_BN_BWD, PC_SGD,
+                 PC_WEIGHT_SNAPSHOT, PC_LAYOUT, PC_HEAD, PC_FILL, PC_COUNT };
+static const char* const kProfNames[PC_COUNT] = {"conv_fwd", "conv_dgrad", "conv_wgrad", "bn_stats", "bn_apply", "bn_bwd",
+                                                 "sgd", "weight_snapshot", "layout", "head", "fill"};
+struct ProfRecord { int cls; double flops, bytes; hipEvent_t e0, e1; };
+struct Profiler {
+  bool on = false;
+  bool overflow = false;
+  std::vector<ProfRecord> recs;
+  std::vector<hipEvent_t> pool;
+  size_t used = 0;
+  hipEvent_t take() {
+    if (used == pool.size()) {
+      hipEvent_t e = nullptr;
+      if (hipEventCreate(&e) != hipSuccess) return nullptr;
+      pool.push_back(e);
+    }
+    return pool[used++];
+  }
+  void reset() { recs.clear(); used = 0; overflow = false; }
+  ~Profiler() { for (hipEvent_t e : pool) (void)hipEventDestroy(e); }
+};
+
 struct fdg_module {
   Plan p;
+  mutable Profiler prof;
   char* ws = nullptr;
   int64_t seq_fwd = 0, seq_bwd = 0;
   bool has_grad = false;
@@ -316,7 +342,52 @@ struct SlotView {
   int32_t* labels() const { return reinterpret_cast<int32_t*>(base + m->p.s_labels); }
 };
 
+// Brackets the launches made in its lifetime with two events when profiling is on.
+struct ProfScope {
+  Profiler* pr = nullptr;
+  hipStream_t s;
+  hipEvent_t e1 = nullptr;
+  ProfScope(const fdg_module* m, int cls, double flops, double bytes, hipStream_t stream) : s(stream) {
+    Profiler& p = m->prof;
+    if (!p.on) return;
+    if (p.recs.size() >= (1u << 18)) { p.overflow = true; return; }
+    hipEvent_t e0 = p.take();
+    e1 = p.take();
+    if (!e0 || !e1) { e1 = nullptr; return; }
+    pr = &p;
+    p.recs.push_back(ProfRecord{cls, flops, bytes, e0, e1});
+    (void)hipEventRecord(e0, s);
+  }
+  ~ProfScope() { if (pr && e1) (void)hipEventRecord(e1, s); }
+};
+
+inline double conv_flops(const ConvShape& c) { return 2.0 * c.N * c.Ho() * c.Wo() * (double)c.Co * c.Ci * c.T; }
+inline double conv_in_elems(const ConvShape& c) { return (double)c.N * c.Hi * c.Wi * c.Cip; }
+inline double conv_out_elems(const ConvShape& c) { return (double)c.N * c.Ho() * c.Wo() * c.Co; }
+inline double conv_w_elems(const ConvShape& c) { return (double)c.Co * c.T * c.Cip; }
+
+hipError_t mconv_forward(const fdg_module* m, const ConvInfo& c, const bf16_t* x, const bf16_t* w, const float* addend,
+                         float* out_f32, bf16_t* out_b16, hipStream_t s) {
+  const double bytes = 2 * conv_in_elems(c.sh) + 2 * conv_w_elems(c.sh) +
+                       conv_out_elems(c.sh) * ((addend ? 4 : 0) + (out_f32 ? 4 : 0) + (out_b16 ? 2 : 0));
+  ProfScope ps(m, PC_CONV_FWD, conv_flops(c.sh), bytes, s);
+  return conv_forward(c.sh, x, w, addend, out_f32, out_b16, s);
+}
+hipError_t mconv_dgrad(const fdg_module* m, const ConvInfo& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
+                       const bf16_t* addmask, float* out_f32, bf16_t* out_b16, hipStream_t s) {
+  const double bytes = 2 * conv_out_elems(c.sh) + 2 * conv_w_elems(c.sh) +
+                       conv_in_elems(c.sh) * ((addend ? 4 : 0) + (addmask ? 2 : 0) + (out_f32 ? 4 : 0) + (out_b16 ? 2 : 0));
+  ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c.sh), bytes, s);
+  return conv_dgrad(c.sh, dy, wt, addend, addmask, out_f32, out_b16, s);
+}
+hipError_t mconv_wgrad(const fdg_module* m, const ConvInfo& c, const bf16_t* x, const bf16_t* dy, hipStream_t s) {
+  const double bytes = 2 * conv_in_elems(c.sh) + 2 * conv_out_elems(c.sh) + 4.0 * c.sh.Co * c.sh.T * c.sh.Ci;
+  ProfScope ps(m, PC_CONV_WGRAD, conv_flops(c.sh), bytes, s);
+  return conv_wgrad(c.sh, x, dy, m->grads() + c.p_off, s);
+}
+
 hipError_t bn_stats(const SlotView& v, const BnInfo& b, const bf16_t* x, hipStream_t s) {
+  ProfScope ps(v.m, PC_BN_STATS, 0, 2.0 * b.M * b.C, s);
   return launch_bn_stats(x, v.sums(b), b.M, b.C, s);
 }
 
@@ -333,6 +404,7 @@ hipError_t bn_apply(const fdg_module* m, const SlotView& v, const BnInfo& b, con
   a.out_f32 = out_f32; a.out_b16 = out_b16;
   a.run_mean = m->running() + b.stat_off; a.run_var = m->running() + b.stat_off + b.C;
   a.M = b.M; a.C = b.C; a.eps = m->p.d.bn_eps; a.momentum = m->p.d.bn_momentum; a.relu = 1;
+  ProfScope ps(m, PC_BN_APPLY, 0, (double)b.M * b.C * (2 + (res ? 4 : 0) + (b2 ? 2 : 0) + (out_f32 ? 4 : 0) + (out_b16 ? 2 : 0)), s);
   return launch_bn_apply(a, s);
 }
 
@@ -347,6 +419,10 @@ hipError_t bn_backward(const fdg_module* m, const SlotView& v, const BnInfo& b, 
   a.addend = addend; a.out_f32 = out_f32; a.out_b16 = out_b16;
   a.dgamma = m->grads() + b.gamma_off; a.dbeta = m->grads() + b.beta_off;
   a.M = b.M; a.C = b.C; a.eps = m->p.d.bn_eps;
+  // the reduce pass reads dy, gate and x; the apply pass reads them again and writes dx
+  const double rd = (dy_f32 ? 4 : 2) + 2 + 2;
+  ProfScope ps(m, PC_BN_BWD, 0, (double)b.M * b.C * (rd + ((out_f32 || out_b16) ? rd : 0) + (addend ? 4 : 0) +
+                                                     (out_f32 ? 4 : 0) + (out_b16 ? 2 : 0)), s);
   hipError_t e = launch_bn_bwd_reduce(a, s);
   if (e != hipSuccess) return e;
   return launch_bn_bwd_apply(a, s);
@@ -424,8 +500,11 @@ fdg_status fdg_forward(fdg_module* m, const float* x_dev, const int32_t* labels_
   SlotView v{m, m->slot(m->seq_fwd)};
   const int N = p.d.n;
   // snapshot of the weights this forward uses (Eq. 10 evaluates the backward at these)
-  FDG_TRY(launch_emit_weights(m->params(), v.warena(), reinterpret_cast<const WeightEmitEntry*>(m->ws + p.o_table),
-                              (int)p.convs.size(), (int)p.emit_blocks, s));
+  {
+    ProfScope ps(m, PC_WEIGHT_SNAPSHOT, 0, 4.0 * p.conv_elems + 2.0 * p.warena_elems, s);
+    FDG_TRY(launch_emit_weights(m->params(), v.warena(), reinterpret_cast<const WeightEmitEntry*>(m->ws + p.o_table),
+                                (int)p.convs.size(), (int)p.emit_blocks, s));
+  }
   if (p.small_count)
     FDG_TRY(hipMemcpyAsync(v.small(), m->params() + p.small_off, p.small_count * 4, hipMemcpyDeviceToDevice, s));
   if (p.stat_floats) FDG_TRY(launch_fill_zero(v.sums(p.bns[0]), align_up(p.stat_floats * 4, 16), s));
@@ -441,23 +520,23 @@ fdg_status fdg_forward(fdg_module* m, const float* x_dev, const int32_t* labels_
     if (L.kind == FDG_STEM_CONV_BN_RELU) {
       const ConvInfo& c0 = p.convs[L.conv[0]];
       const BnInfo& b0 = p.bns[L.bn[0]];
-      FDG_TRY(conv_forward(c0.sh, cur_b, v.W(c0), nullptr, nullptr, v.act(L.act[0]), s));
+      FDG_TRY(mconv_forward(m, c0, cur_b, v.W(c0), nullptr, nullptr, v.act(L.act[0]), s));
       FDG_TRY(bn_stats(v, b0, v.act(L.act[0]), s));
       FDG_TRY(bn_apply(m, v, b0, v.act(L.act[0]), nullptr, nullptr, nullptr, m->S(nxt), v.act(L.out_b), s));
     } else if (L.kind == FDG_BASIC_POSTACT) {
       const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]];
       const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]];
       bf16_t *t_c1 = v.act(L.act[0]), *t_a1 = v.act(L.act[1]), *t_c2 = v.act(L.act[2]);
-      FDG_TRY(conv_forward(c1.sh, cur_b, v.W(c1), nullptr, nullptr, t_c1, s));
+      FDG_TRY(mconv_forward(m, c1, cur_b, v.W(c1), nullptr, nullptr, t_c1, s));
       FDG_TRY(bn_stats(v, b1, t_c1, s));
       FDG_TRY(bn_apply(m, v, b1, t_c1, nullptr, nullptr, nullptr, nullptr, t_a1, s));
-      FDG_TRY(conv_forward(c2.sh, t_a1, v.W(c2), nullptr, nullptr, t_c2, s));
+      FDG_TRY(mconv_forward(m, c2, t_a1, v.W(c2), nullptr, nullptr, t_c2, s));
       FDG_TRY(bn_stats(v, b2, t_c2, s));
       if (L.projects) {
         const ConvInfo& cp = p.convs[L.conv[2]];
         const BnInfo& bp = p.bns[L.bn[2]];
         bf16_t* t_p = v.act(L.act[3]);
-        FDG_TRY(conv_forward(cp.sh, cur_b, v.W(cp), nullptr, nullptr, t_p, s));
+        FDG_TRY(mconv_forward(m, cp, cur_b, v.W(cp), nullptr, nullptr, t_p, s));
         FDG_TRY(bn_stats(v, bp, t_p, s));
         FDG_TRY(bn_apply(m, v, b2, t_c2, nullptr, &bp, t_p, m->S(nxt), v.act(L.out_b), s));
       } else {
@@ -469,16 +548,16 @@ fdg_status fdg_forward(fdg_module* m, const float* x_dev, const int32_t* labels_
       bf16_t *t_o1 = v.act(L.act[0]), *t_c1 = v.act(L.act[1]), *t_o2 = v.act(L.act[2]);
       FDG_TRY(bn_stats(v, b1, cur_b, s));
       FDG_TRY(bn_apply(m, v, b1, cur_b, nullptr, nullptr, nullptr, nullptr, t_o1, s));
-      FDG_TRY(conv_forward(c1.sh, t_o1, v.W(c1), nullptr, nullptr, t_c1, s));
+      FDG_TRY(mconv_forward(m, c1, t_o1, v.W(c1), nullptr, nullptr, t_c1, s));
       FDG_TRY(bn_stats(v, b2, t_c1, s));
       FDG_TRY(bn_apply(m, v, b2, t_c1, nullptr, nullptr, nullptr, nullptr, t_o2, s));
       const float* shortcut = m->S(cur);
       if (L.projects) {
         const ConvInfo& cp = p.convs[L.conv[2]];
-        FDG_TRY(conv_forward(cp.sh, t_o1, v.W(cp), nullptr, m->TP(), nullptr, s));
+        FDG_TRY(mconv_forward(m, cp, t_o1, v.W(cp), nullptr, m->TP(), nullptr, s));
         shortcut = m->TP();
       }
-      FDG_TRY(conv_forward(c2.sh, t_o2, v.W(c2), shortcut, m->S(nxt), v.act(L.out_b), s));
+      FDG_TRY(mconv_forward(m, c2, t_o2, v.W(c2), shortcut, m->S(nxt), v.act(L.out_b), s));
     } else {  // heads
       const bf16_t* o = cur_b;
       if (L.kind == FDG_HEAD_PREACT) {
@@ -536,48 +615,48 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
       const ConvInfo& c0 = p.convs[L.conv[0]];
       const BnInfo& b0 = p.bns[L.bn[0]];
       FDG_TRY(bn_backward(m, v, b0, m->G(cur), true, v.act(L.out_b), v.act(L.act[0]), nullptr, nullptr, m->T(0), s));
-      FDG_TRY(conv_wgrad(c0.sh, in_b, m->T(0), m->grads() + c0.p_off, s));
-      if (need_dx) FDG_TRY(conv_dgrad(c0.sh, m->T(0), v.Wt(c0), nullptr, nullptr, m->G(nxt), m->GB(nxt), s));
+      FDG_TRY(mconv_wgrad(m, c0, in_b, m->T(0), s));
+      if (need_dx) FDG_TRY(mconv_dgrad(m, c0, m->T(0), v.Wt(c0), nullptr, nullptr, m->G(nxt), m->GB(nxt), s));
     } else if (L.kind == FDG_BASIC_POSTACT) {
       const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]];
       const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]];
       const bf16_t *t_c1 = v.act(L.act[0]), *t_a1 = v.act(L.act[1]), *t_c2 = v.act(L.act[2]), *t_y = v.act(L.out_b);
       // final ReLU mask (y > 0) then BN2
       FDG_TRY(bn_backward(m, v, b2, m->G(cur), true, t_y, t_c2, nullptr, nullptr, m->T(0), s));
-      FDG_TRY(conv_wgrad(c2.sh, t_a1, m->T(0), m->grads() + c2.p_off, s));
-      FDG_TRY(conv_dgrad(c2.sh, m->T(0), v.Wt(c2), nullptr, nullptr, nullptr, m->T(1), s));
+      FDG_TRY(mconv_wgrad(m, c2, t_a1, m->T(0), s));
+      FDG_TRY(mconv_dgrad(m, c2, m->T(0), v.Wt(c2), nullptr, nullptr, nullptr, m->T(1), s));
       FDG_TRY(bn_backward(m, v, b1, m->T(1), false, t_a1, t_c1, nullptr, nullptr, m->T(0), s));
-      FDG_TRY(conv_wgrad(c1.sh, in_b, m->T(0), m->grads() + c1.p_off, s));
+      FDG_TRY(mconv_wgrad(m, c1, in_b, m->T(0), s));
       if (L.projects) {
         const ConvInfo& cp = p.convs[L.conv[2]];
         const BnInfo& bp = p.bns[L.bn[2]];
         FDG_TRY(bn_backward(m, v, bp, m->G(cur), true, t_y, v.act(L.act[3]), nullptr, nullptr, m->T(1), s));
-        FDG_TRY(conv_wgrad(cp.sh, in_b, m->T(1), m->grads() + cp.p_off, s));
+        FDG_TRY(mconv_wgrad(m, cp, in_b, m->T(1), s));
         if (need_dx) {
-          FDG_TRY(conv_dgrad(cp.sh, m->T(1), v.Wt(cp), nullptr, nullptr, m->TP(), nullptr, s));
-          FDG_TRY(conv_dgrad(c1.sh, m->T(0), v.Wt(c1), m->TP(), nullptr, m->G(nxt), m->GB(nxt), s));
+          FDG_TRY(mconv_dgrad(m, cp, m->T(1), v.Wt(cp), nullptr, nullptr, m->TP(), nullptr, s));
+          FDG_TRY(mconv_dgrad(m, c1, m->T(0), v.Wt(c1), m->TP(), nullptr, m->G(nxt), m->GB(nxt), s));
         }
       } else if (need_dx) {
         // identity shortcut: the masked incoming gradient joins the branch gradient
-        FDG_TRY(conv_dgrad(c1.sh, m->T(0), v.Wt(c1), m->G(cur), t_y, m->G(nxt), m->GB(nxt), s));
+        FDG_TRY(mconv_dgrad(m, c1, m->T(0), v.Wt(c1), m->G(cur), t_y, m->G(nxt), m->GB(nxt), s));
       }
     } else {  // pre-activation block: y = conv2(o2) + shortcut
       const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]];
       const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]];
       const bf16_t *t_o1 = v.act(L.act[0]), *t_c1 = v.act(L.act[1]), *t_o2 = v.act(L.act[2]);
-      FDG_TRY(conv_wgrad(c2.sh, t_o2, m->GB(cur), m->grads() + c2.p_off, s));
-      FDG_TRY(conv_dgrad(c2.sh, m->GB(cur), v.Wt(c2), nullptr, nullptr, nullptr, m->T(0), s));
+      FDG_TRY(mconv_wgrad(m, c2, t_o2, m->GB(cur), s));
+      FDG_TRY(mconv_dgrad(m, c2, m->GB(cur), v.Wt(c2), nullptr, nullptr, nullptr, m->T(0), s));
       FDG_TRY(bn_backward(m, v, b2, m->T(0), false, t_o2, t_c1, nullptr, nullptr, m->T(1), s));
-      FDG_TRY(conv_wgrad(c1.sh, t_o1, m->T(1), m->grads() + c1.p_off, s));
+      FDG_TRY(mconv_wgrad(m, c1, t_o1, m->T(1), s));
       if (L.projects) {
         const ConvInfo& cp = p.convs[L.conv[2]];
-        FDG_TRY(conv_wgrad(cp.sh, t_o1, m->GB(cur), m->grads() + cp.p_off, s));
-        FDG_TRY(conv_dgrad(cp.sh, m->GB(cur), v.Wt(cp), nullptr, nullptr, m->TP(), nullptr, s));
-        FDG_TRY(conv_dgrad(c1.sh, m->T(1), v.Wt(c1), m->TP(), nullptr, nullptr, m->T(0), s));
+        FDG_TRY(mconv_wgrad(m, cp, t_o1, m->GB(cur), s));
+        FDG_TRY(mconv_dgrad(m, cp, m->GB(cur), v.Wt(cp), nullptr, nullptr, m->TP(), nullptr, s));
+        FDG_TRY(mconv_dgrad(m, c1, m->T(1), v.Wt(c1), m->TP(), nullptr, nullptr, m->T(0), s));
         FDG_TRY(bn_backward(m, v, b1, m->T(0), false, t_o1, in_b, nullptr, need_dx ? m->G(nxt) : nullptr,
                             need_dx ? m->GB(nxt) : nullptr, s));
       } else {
-        FDG_TRY(conv_dgrad(c1.sh, m->T(1), v.Wt(c1), nullptr, nullptr, nullptr, m->T(0), s));
+        FDG_TRY(mconv_dgrad(m, c1, m->T(1), v.Wt(c1), nullptr, nullptr, nullptr, m->T(0), s));
         FDG_TRY(bn_backward(m, v, b1, m->T(0), false, t_o1, in_b, m->G(cur), need_dx ? m->G(nxt) : nullptr,
                             need_dx ? m->GB(nxt) : nullptr, s));
       }
@@ -596,7 +675,10 @@ fdg_status fdg_update(fdg_module* m, float lr, void* hip_stream) {
   if (!m->has_grad) return FDG_ERR_NO_GRAD;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   m->last_stream = s;
-  FDG_TRY(launch_sgd(m->params(), m->mom(), m->grads(), m->p.P, lr, m->p.d.momentum, m->p.d.weight_decay, s));
+  {
+    ProfScope ps(m, PC_SGD, 0, 20.0 * m->p.P, s);   // read theta, v, g; write theta, v
+    FDG_TRY(launch_sgd(m->params(), m->mom(), m->grads(), m->p.P, lr, m->p.d.momentum, m->p.d.weight_decay, s));
+  }
   m->has_grad = false;
   return FDG_OK;
 }
@@ -694,6 +776,40 @@ fdg_status fdg_queue_state(const fdg_module* m, int32_t* outstanding, int64_t* o
   if (oldest_seq) *oldest_seq = n ? m->seq_bwd : -1;
   if (newest_seq) *newest_seq = n ? m->seq_fwd - 1 : -1;
   return FDG_OK;
+}
+
+fdg_status fdg_profile_enable(fdg_module* m, int enable) {
+  if (!m) return FDG_ERR_INVALID_ARG;
+  FDG_TRY(hipStreamSynchronize(m->last_stream));
+  m->prof.reset();
+  m->prof.on = enable != 0;
+  return FDG_OK;
+}
+
+fdg_status fdg_profile_read(fdg_module* m, fdg_profile_entry* out, int32_t capacity, int32_t* count) {
+  if (!m || !count || (capacity > 0 && !out)) return FDG_ERR_INVALID_ARG;
+  FDG_TRY(hipStreamSynchronize(m->last_stream));
+  fdg_profile_entry acc[PC_COUNT];
+  for (int i = 0; i < PC_COUNT; ++i) {
+    acc[i] = fdg_profile_entry{};
+    snprintf(acc[i].name, sizeof(acc[i].name), "%s", kProfNames[i]);
+  }
+  for (const ProfRecord& r : m->prof.recs) {
+    float ms = 0.f;
+    FDG_TRY(hipEventElapsedTime(&ms, r.e0, r.e1));
+    acc[r.cls].calls += 1;
+    acc[r.cls].total_ms += ms;
+    acc[r.cls].flops += r.flops;
+    acc[r.cls].bytes += r.bytes;
+  }
+  int n = 0;
+  for (int i = 0; i < PC_COUNT; ++i) {
+    if (acc[i].calls == 0) continue;
+    if (n < capacity) out[n] = acc[i];
+    ++n;
+  }
+  *count = n;
+  return m->prof.overflow ? FDG_ERR_UNSUPPORTED : FDG_OK;
 }
 
 const char* fdg_status_string(fdg_status s) {
