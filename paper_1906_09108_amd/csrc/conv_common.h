@@ -1,0 +1,65 @@
+// Pieces shared by the convolution kernels: MFMA wrapper, bf16 packing, and the output stage.
+#pragma once
+#include "fdg_internal.h"
+
+namespace fdg {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  bf16_t l = (bf16_t)lo, h = (bf16_t)hi;
+  return (uint32_t)__builtin_bit_cast(uint16_t, l) | ((uint32_t)__builtin_bit_cast(uint16_t, h) << 16);
+}
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __builtin_bit_cast(float, u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __builtin_bit_cast(float, u & 0xffff0000u); }
+
+// Output stage of a gather-form convolution.  acc[i][j] is the 16x16 result block of channel group i
+// and pixel group j of this wave: lane l holds channels 4*(l>>4) .. +3 of pixel (l & 15).  Adds the
+// optional fp32 addend (gated by addmask > 0 when given) and writes fp32 and/or bf16.
+template <int FM, int FN>
+__device__ __forceinline__ void store_tile(const GatherConvArgs& a, const f32x4 (&acc)[FN][FM], int m_base, int c_base,
+                                           int lane) {
+  const int Mtot = a.N * a.OH * a.OW;
+#pragma unroll
+  for (int j = 0; j < FM; ++j) {
+    const int m = m_base + j * 16 + (lane & 15);
+    if (m >= Mtot) continue;
+    const int ow = m % a.OW, t2 = m / a.OW, oh = t2 % a.OH, n = t2 / a.OH;
+    const size_t opix = ((size_t)n * a.OHf + oh * a.out_stride + a.ooh) * a.OWf + ow * a.out_stride + a.oow;
+#pragma unroll
+    for (int i = 0; i < FN; ++i) {
+      const int c = c_base + i * 16 + 4 * (lane >> 4);
+      if (c >= a.Co) continue;
+      const size_t o = opix * a.Co + c;
+      f32x4 v = acc[i][j];
+      if (a.addend) {
+        float4 ad = *reinterpret_cast<const float4*>(a.addend + o);
+        if (a.addmask) {
+          const uint2 mk = *reinterpret_cast<const uint2*>(a.addmask + o);
+          if (!(bf16_lo(mk.x) > 0.f)) ad.x = 0.f;
+          if (!(bf16_hi(mk.x) > 0.f)) ad.y = 0.f;
+          if (!(bf16_lo(mk.y) > 0.f)) ad.z = 0.f;
+          if (!(bf16_hi(mk.y) > 0.f)) ad.w = 0.f;
+        }
+        v[0] += ad.x;
+        v[1] += ad.y;
+        v[2] += ad.z;
+        v[3] += ad.w;
+      }
+      if (a.out_f32) *reinterpret_cast<float4*>(a.out_f32 + o) = make_float4(v[0], v[1], v[2], v[3]);
+      if (a.out_b16)
+        *reinterpret_cast<uint2*>(a.out_b16 + o) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+    }
+  }
+}
+
+// The wide-channel kernel (conv_wide_kernels.hip): input channels a multiple of 64.
+bool conv_gather_wide_applies(const GatherConvArgs& a);
+hipError_t launch_conv_gather_wide(const GatherConvArgs& a, hipStream_t s);
+
+}  // namespace fdg

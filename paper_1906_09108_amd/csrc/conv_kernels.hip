@@ -12,23 +12,9 @@
 // MFMA operand layout used throughout (16x16x32, 64 lanes): lane l supplies row (l & 15) of A and
 // column (l & 15) of B, each with the 8 consecutive k values 8*(l >> 4) .. +7; lane l receives
 // D[4*(l >> 4) + v][l & 15] in accumulator component v.
-#include "fdg_internal.h"
+#include "conv_common.h"
 
 namespace fdg {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
-}
-
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  bf16_t l = (bf16_t)lo, h = (bf16_t)hi;
-  return (uint32_t)__builtin_bit_cast(uint16_t, l) | ((uint32_t)__builtin_bit_cast(uint16_t, h) << 16);
-}
-__device__ __forceinline__ float bf16_lo(uint32_t u) { return __builtin_bit_cast(float, u << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t u) { return __builtin_bit_cast(float, u & 0xffff0000u); }
 
 // ------------------------------------------------------------------------------------------------
 // gather-form convolution
@@ -146,38 +132,7 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(GatherConvArgs a) {
     __syncthreads();
   }
 
-  // epilogue: lane holds 4 consecutive channels of one pixel per accumulator
-#pragma unroll
-  for (int j = 0; j < FM; ++j) {
-    const int m = m0 + wave_m * TM + j * 16 + (lane & 15);
-    if (m >= Mtot) continue;
-    const int ow = m % a.OW, t2 = m / a.OW, oh = t2 % a.OH, n = t2 / a.OH;
-    const size_t opix = ((size_t)n * a.OHf + oh * a.out_stride + a.ooh) * a.OWf + ow * a.out_stride + a.oow;
-#pragma unroll
-    for (int i = 0; i < FN; ++i) {
-      const int c = c0 + wave_n * TN + i * 16 + 4 * (lane >> 4);
-      if (c >= a.Co) continue;
-      const size_t o = opix * a.Co + c;
-      f32x4 v = acc[i][j];
-      if (a.addend) {
-        float4 ad = *reinterpret_cast<const float4*>(a.addend + o);
-        if (a.addmask) {
-          const uint2 mk = *reinterpret_cast<const uint2*>(a.addmask + o);
-          if (!(bf16_lo(mk.x) > 0.f)) ad.x = 0.f;
-          if (!(bf16_hi(mk.x) > 0.f)) ad.y = 0.f;
-          if (!(bf16_lo(mk.y) > 0.f)) ad.z = 0.f;
-          if (!(bf16_hi(mk.y) > 0.f)) ad.w = 0.f;
-        }
-        v[0] += ad.x;
-        v[1] += ad.y;
-        v[2] += ad.z;
-        v[3] += ad.w;
-      }
-      if (a.out_f32) *reinterpret_cast<float4*>(a.out_f32 + o) = make_float4(v[0], v[1], v[2], v[3]);
-      if (a.out_b16)
-        *reinterpret_cast<uint2*>(a.out_b16 + o) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
-    }
-  }
+  store_tile<FM, FN>(a, acc, m0 + wave_m * TM, c0 + wave_n * TN, lane);
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N>
@@ -191,6 +146,7 @@ static hipError_t run_gather(const GatherConvArgs& a, hipStream_t s) {
 hipError_t launch_conv_gather(const GatherConvArgs& a, hipStream_t s) {
   if (a.Ci % 8 != 0 || a.Co % 4 != 0 || a.ntaps < 0 || a.ntaps > 9 || a.N * a.OH * a.OW <= 0 || a.Kw % 8 != 0)
     return hipErrorInvalidValue;
+  if (conv_gather_wide_applies(a)) return launch_conv_gather_wide(a, s);
   if (a.Co <= 16) return run_gather<256, 16, 4, 1>(a, s);
   if (a.Co <= 32) return run_gather<256, 32, 4, 1>(a, s);
   if (a.Co <= 64) return run_gather<128, 64, 2, 2>(a, s);

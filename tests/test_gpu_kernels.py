@@ -60,6 +60,14 @@ CONV_CASES = [  # n, h, w, ci, co, ksize, stride
     (8, 8, 8, 320, 320, 3, 1),
     (4, 16, 16, 160, 320, 3, 2),
     (16, 32, 32, 16, 16, 3, 1),
+    # wide layers (input channels a multiple of 64): the direct-to-LDS kernel, both tile widths, ragged pixels
+    (2, 8, 8, 64, 160, 3, 1),
+    (3, 7, 5, 128, 128, 3, 1),
+    (2, 8, 8, 320, 640, 3, 2),
+    (3, 9, 7, 192, 320, 3, 2),
+    (2, 8, 8, 320, 640, 1, 2),
+    (5, 4, 4, 128, 192, 1, 1),
+    (16, 8, 8, 640, 640, 3, 1),
 ]
 
 
