@@ -61,5 +61,8 @@ __device__ __forceinline__ void store_tile(const GatherConvArgs& a, const f32x4 
 // The wide-channel kernel (conv_wide_kernels.hip): input channels a multiple of 64.
 bool conv_gather_wide_applies(const GatherConvArgs& a);
 hipError_t launch_conv_gather_wide(const GatherConvArgs& a, hipStream_t s);
+// The wide-channel weight gradient: output and input channels multiples of 160, output width dividing 64.
+bool conv_wgrad_wide_applies(const WgradArgs& a);
+hipError_t launch_conv_wgrad_wide(const WgradArgs& a, hipStream_t s);
 
 }  // namespace fdg

@@ -327,6 +327,7 @@ static hipError_t run_wgrad(const WgradArgs& a, hipStream_t s) {
 hipError_t launch_conv_wgrad(const WgradArgs& a, hipStream_t s) {
   if (a.Co % 8 != 0 || a.Cx % 8 != 0 || a.Ci > a.Cx || a.ntaps < 1 || a.ntaps > 9 || a.N * a.OH * a.OW <= 0)
     return hipErrorInvalidValue;
+  if (conv_wgrad_wide_applies(a)) return launch_conv_wgrad_wide(a, s);
   if (a.Co <= 64 && a.Cx <= 64) return run_wgrad<32, 32, 1, 1, 4>(a, s);
   return run_wgrad<128, 128, 2, 2, 1>(a, s);
 }

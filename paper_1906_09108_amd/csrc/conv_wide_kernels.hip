@@ -176,4 +176,202 @@ hipError_t launch_conv_gather_wide(const GatherConvArgs& a, hipStream_t s) {
   return run_wide<128, 128, 2, 2, 4>(a, s);
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// Weight gradient for wide layers: dw[co, tap, ci] += sum_pixel dy[pixel, co] * x[pixel + tap, ci]
+// ------------------------------------------------------------------------------------------------
+// Both operands are [pixel][channel] in memory while the MFMA wants, per lane, 8 consecutive pixels of one
+// channel.  The tiles are landed in LDS as they are (direct global-to-LDS loads, 64 pixels x 160 channels
+// of dy and of the shifted x per chunk) and read with ds_read_b64_tr_b16, which transposes on the way
+// out: in a group of 16 lanes, lanes 4j..4j+3 address 16 consecutive bf16 of pixel j, and lane i
+// receives element i of pixels 0..3.  Two such reads give a lane its 8 pixels (k values); which 8 is
+// free as long as both operands agree: lane group g takes pixels 4g..4g+3 and 16+4g..16+4g+3 of a
+// 32-pixel step.  Rows are 320 bytes, so 4 consecutive pixels fall into 4 different 64-byte windows of
+// the banks; the 32-byte slot index is XORed with bit 2 of the pixel so that 8 consecutive pixels are
+// conflict free.  One workgroup owns a 160 x 160 block of one tap and a range of pixel chunks; partial
+// sums are added with fp32 atomics.
+typedef short v4s16 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ bf16x8 lds_read_tr8(const unsigned char* p) {
+  const v4s16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s16*)p);
+  const v4s16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s16*)(p + 16 * 320));
+  typedef short v8s16 __attribute__((ext_vector_type(8)));
+  const v8s16 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, both);
+}
+
+struct WgradWideLaunch {
+  int co_tiles, ci_tiles, splits, chunks_per_split;
+};
+
+template <int STAGES>
+__global__ __launch_bounds__(256) void conv_wgrad_dma_kernel(WgradArgs a, WgradWideLaunch L) {
+  constexpr int BC = 160;                  // channels per operand tile
+  constexpr int BKP = 64;                  // pixels per chunk
+  constexpr int ROWB = BC * 2;             // 320 bytes per pixel row
+  constexpr int UPR = BC / 8;              // 16-byte units per row (20)
+  constexpr int PART = BKP * ROWB;         // bytes of one operand tile (20480)
+  constexpr int JP = BKP * UPR / 256;      // DMA instructions per thread per operand (5)
+  constexpr int NJ = 2 * JP;
+  constexpr int F = 5;                     // 80 channels per wave side = 5 MFMA blocks
+  static_assert((STAGES - 2) * NJ < 64, "vmcnt range");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // STAGES * 2 * PART
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave & 1, wn = wave >> 1;
+  const int Mtot = a.N * a.OH * a.OW;
+
+  // workgroup -> (split, tap, co tile, ci tile); XCD aware as in the forward kernel
+  int t = blockIdx.x;
+  const int total = gridDim.x;
+  if ((total & 7) == 0) t = (blockIdx.x & 7) * (total >> 3) + (blockIdx.x >> 3);
+  const int ci_t = t % L.ci_tiles; t /= L.ci_tiles;
+  const int co_t = t % L.co_tiles; t /= L.co_tiles;
+  const int tapi = t % a.ntaps;
+  const int split = t / a.ntaps;
+  const int co0 = co_t * BC, ci0 = ci_t * BC;
+  const int tp = a.tap[tapi];
+  const int dh = (tp & 0xff) - 8, dw = ((tp >> 8) & 0xff) - 8;
+  const int total_chunks = (Mtot + BKP - 1) / BKP;
+  const int chunk_lo = split * L.chunks_per_split;
+  const int chunk_hi = min(total_chunks, chunk_lo + L.chunks_per_split);
+  const int nchunks = chunk_hi - chunk_lo;
+  if (nchunks <= 0) return;
+
+  // ---- per-thread DMA sources ----
+  int arow[JP];              // pixel row within the chunk, dy tile
+  const char* asrc[JP];      // dy address of pixel row 0 of chunk 0 for this lane's unit
+  int bm[JP], bn_[JP], boh[JP], biw[JP];   // x tile: running pixel index, image, output row, input column (or -1)
+  int bcol[JP];              // byte offset of this lane's channel unit within a pixel
+#pragma unroll
+  for (int j = 0; j < JP; ++j) {
+    const int P = 64 * (4 * j + wave) + lane;
+    const int r = P / UPR, up = P % UPR;
+    const int u = 2 * ((up >> 1) ^ ((r >> 2) & 1)) + (up & 1);
+    arow[j] = r;
+    asrc[j] = reinterpret_cast<const char*>(a.dy) + ((size_t)r * a.Co + co0 + u * 8) * 2;
+    const int m = chunk_lo * BKP + r;
+    bm[j] = m;
+    const int mm = m < Mtot ? m : 0;
+    const int ow = mm % a.OW, t2 = mm / a.OW;
+    boh[j] = t2 % a.OH;
+    bn_[j] = t2 / a.OH;
+    const int iw = ow * a.stride + dw;
+    biw[j] = ((unsigned)iw < (unsigned)a.Wi) ? iw : -1;
+    bcol[j] = (ci0 + u * 8) * 2;
+  }
+  const char* zero = reinterpret_cast<const char*>(g_zero_word);
+  const int d_oh = BKP / a.OW;   // the launcher guarantees OW divides 64
+
+  auto issue = [&](int c) {   // c = chunk index relative to chunk_lo
+    unsigned char* stage = smem + (size_t)(c % STAGES) * (2 * PART);
+    const size_t abase = (size_t)(chunk_lo + c) * BKP * a.Co * 2;
+#pragma unroll
+    for (int j = 0; j < JP; ++j) {
+      const bool ok = (chunk_lo + c) * BKP + arow[j] < Mtot;
+      dma16(ok ? asrc[j] + abase : zero, stage + (size_t)(64 * (4 * j + wave)) * 16);
+    }
+#pragma unroll
+    for (int j = 0; j < JP; ++j) {
+      const int ih = boh[j] * a.stride + dh;
+      const bool ok = bm[j] < Mtot && biw[j] >= 0 && (unsigned)ih < (unsigned)a.Hi;
+      const char* g = reinterpret_cast<const char*>(a.x) +
+                      (((size_t)bn_[j] * a.Hi + ih) * a.Wi + biw[j]) * (size_t)a.Cx * 2 + bcol[j];
+      dma16(ok ? g : zero, stage + PART + (size_t)(64 * (4 * j + wave)) * 16);
+      // advance this row to the next chunk
+      bm[j] += BKP;
+      boh[j] += d_oh;
+      while (boh[j] >= a.OH) {
+        boh[j] -= a.OH;
+        bn_[j] += 1;
+      }
+    }
+  };
+
+  f32x4 acc[F][F];
+#pragma unroll
+  for (int i = 0; i < F; ++i)
+#pragma unroll
+    for (int j = 0; j < F; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // this lane's read address inside a tile for MFMA block f and k-step ks:
+  //   pixel r = 32*ks + 4*(lane>>4) + ((lane&15)>>2), channels cbase + 16*f + 4*(lane&3)
+  const int g = lane >> 4, i16 = lane & 15;
+  const int r_in_step = 4 * g + (i16 >> 2);
+
+#pragma unroll
+  for (int p = 0; p < STAGES - 1; ++p)
+    if (p < nchunks) issue(p);
+
+  for (int c = 0; c < nchunks; ++c) {
+    if (c + STAGES - 2 < nchunks) wait_vmcnt<(STAGES - 2) * NJ>(); else wait_vmcnt<0>();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (c + STAGES - 1 < nchunks) issue(c + STAGES - 1);
+    const unsigned char* stage = smem + (size_t)(c % STAGES) * (2 * PART);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const int r = 32 * ks + r_in_step;
+      const int swz = (r >> 2) & 1;   // the same for r and r + 16
+      bf16x8 fa[F], fb[F];
+#pragma unroll
+      for (int f = 0; f < F; ++f) {
+        const int slot_a = ((wm * 80 + f * 16) >> 4) ^ swz, slot_b = ((wn * 80 + f * 16) >> 4) ^ swz;
+        fa[f] = lds_read_tr8(stage + r * ROWB + slot_a * 32 + (i16 & 3) * 8);
+        fb[f] = lds_read_tr8(stage + PART + r * ROWB + slot_b * 32 + (i16 & 3) * 8);
+      }
+#pragma unroll
+      for (int i = 0; i < F; ++i)
+#pragma unroll
+        for (int j = 0; j < F; ++j) acc[i][j] = mfma16(fa[i], fb[j], acc[i][j]);
+    }
+  }
+
+  // D[co][ci]: lane holds co = 4*(lane>>4)+v, ci = lane&15 of each 16x16 block
+#pragma unroll
+  for (int i = 0; i < F; ++i)
+#pragma unroll
+    for (int j = 0; j < F; ++j) {
+      const int ci = ci0 + wn * 80 + j * 16 + (lane & 15);
+      if (ci >= a.Ci) continue;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int co = co0 + wm * 80 + i * 16 + 4 * (lane >> 4) + v;
+        if (co < a.Co) atomicAdd(a.dw + ((size_t)co * a.ntaps + tapi) * a.Ci + ci, acc[i][j][v]);
+      }
+    }
+}
+
+bool conv_wgrad_wide_applies(const WgradArgs& a) {
+  return a.Co % 160 == 0 && a.Ci % 160 == 0 && a.Cx == a.Ci && a.OW >= 1 && 64 % a.OW == 0 && a.ntaps >= 1;
+}
+
+hipError_t launch_conv_wgrad_wide(const WgradArgs& a, hipStream_t s) {
+  if (!conv_wgrad_wide_applies(a) || a.N * a.OH * a.OW <= 0) return hipErrorInvalidValue;
+  constexpr int STAGES = 3;
+  constexpr size_t lds = (size_t)STAGES * 2 * 64 * 320;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad_dma_kernel<STAGES>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int Mtot = a.N * a.OH * a.OW;
+  WgradWideLaunch L;
+  L.co_tiles = a.Co / 160;
+  L.ci_tiles = a.Ci / 160;
+  const int tiles = L.co_tiles * L.ci_tiles * a.ntaps;
+  const int total_chunks = (Mtot + 63) / 64;
+  int splits = 1024 / tiles;                       // about four rounds of the 256 compute units
+  if (splits > total_chunks / 4) splits = total_chunks / 4;
+  if (splits < 1) splits = 1;
+  L.chunks_per_split = (total_chunks + splits - 1) / splits;
+  L.splits = (total_chunks + L.chunks_per_split - 1) / L.chunks_per_split;
+  hipLaunchKernelGGL((conv_wgrad_dma_kernel<STAGES>), dim3(tiles * L.splits), dim3(256), lds, s, a, L);
+  return hipGetLastError();
+}
+
 }  // namespace fdg

@@ -68,6 +68,10 @@ CONV_CASES = [  # n, h, w, ci, co, ksize, stride
     (2, 8, 8, 320, 640, 1, 2),
     (5, 4, 4, 128, 192, 1, 1),
     (16, 8, 8, 640, 640, 3, 1),
+    # channel counts that are multiples of 160: the transposing direct-to-LDS weight-gradient kernel
+    (3, 4, 4, 160, 160, 3, 1),
+    (5, 8, 8, 160, 320, 3, 1),
+    (3, 16, 16, 320, 160, 3, 2),
 ]
 
 
