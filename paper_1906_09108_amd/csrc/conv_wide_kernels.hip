@@ -12,6 +12,8 @@
 //     workgroups for the 8x8 and 16x16 stages, i.e. whole rounds of the 256 compute units;
 //   * workgroups are numbered so that the eight XCDs (workgroup id mod 8) each own a contiguous range of
 //     pixel tiles with all of their channel tiles, keeping operand reuse inside one L2.
+#include <cstdlib>
+
 #include "conv_common.h"
 
 namespace fdg {
@@ -365,7 +367,8 @@ hipError_t launch_conv_wgrad_wide(const WgradArgs& a, hipStream_t s) {
   L.ci_tiles = a.Ci / 160;
   const int tiles = L.co_tiles * L.ci_tiles * a.ntaps;
   const int total_chunks = (Mtot + 63) / 64;
-  int splits = 1024 / tiles;                       // about four rounds of the 256 compute units
+  static const int target_wgs = [] { const char* e = getenv("FDG_WGRAD_WGS"); return e ? atoi(e) : 512; }();
+  int splits = target_wgs / tiles;                 // about two rounds of the 256 compute units (more splits = more atomics)
   if (splits > total_chunks / 4) splits = total_chunks / 4;
   if (splits < 1) splits = 1;
   L.chunks_per_split = (total_chunks + splits - 1) / splits;
