@@ -29,9 +29,11 @@ extern "C" {
 
 /* y = conv(x, w) (+ addend):  y[n,ho,wo,o] = sum_{r,q,i} x[n, ho*s+r-p, wo*s+q-p, i] * w[o,r,q,i].
  *   x_b16 [n,h,w,cip]; w_b16 [co][ksize*ksize][cip]; addend_f32 optional [n,ho,wo,co];
- *   y_f32 / y_b16 optional outputs (at least one).                                                 */
+ *   y_f32 / y_b16 optional outputs (at least one);  stats_f32 optional [2*co], zero it first:
+ *   stats[o] += sum of bf16(y[..,o]), stats[co+o] += sum of bf16(y[..,o])^2 over all pixels -- the
+ *   batch-norm statistics of the tensor just written, taken in the epilogue instead of a second pass. */
 int fdgk_conv_fwd(const void* x_b16, const void* w_b16, const float* addend_f32, float* y_f32, void* y_b16,
-                  int n, int h, int w, int ci, int co, int ksize, int stride, void* hip_stream);
+                  float* stats_f32, int n, int h, int w, int ci, int co, int ksize, int stride, void* hip_stream);
 
 /* Data gradient, the adjoint of fdgk_conv_fwd in x:
  *   dx[n,hi,wi,i] = sum_{o,r,q : hi = ho*s+r-p, wi = wo*s+q-p} dy[n,ho,wo,o] * w[o,r,q,i]  (+ addend)

@@ -21,10 +21,18 @@ __device__ __forceinline__ float bf16_hi(uint32_t u) { return __builtin_bit_cast
 // Output stage of a gather-form convolution.  acc[i][j] is the 16x16 result block of channel group i
 // and pixel group j of this wave: lane l holds channels 4*(l>>4) .. +3 of pixel (l & 15).  Adds the
 // optional fp32 addend (gated by addmask > 0 when given) and writes fp32 and/or bf16.
-template <int FM, int FN>
-__device__ __forceinline__ void store_tile(const GatherConvArgs& a, const f32x4 (&acc)[FN][FM], int m_base, int c_base,
-                                           int lane) {
+// BN = channels of the workgroup tile starting at c_tile; this wave's channels start at c_tile + c_wave.
+// Must be called by all threads of the workgroup (the statistics are combined through LDS).
+template <int FM, int FN, int BN>
+__device__ __forceinline__ void store_tile(const GatherConvArgs& a, const f32x4 (&acc)[FN][FM], int m_base, int c_tile,
+                                           int c_wave, int lane) {
   const int Mtot = a.N * a.OH * a.OW;
+  const int c_base = c_tile + c_wave;
+  float s1[FN][4], s2[FN][4];   // batch-norm statistics of this lane's pixels (only with a.stats)
+#pragma unroll
+  for (int i = 0; i < FN; ++i)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) s1[i][v] = s2[i][v] = 0.f;
 #pragma unroll
   for (int j = 0; j < FM; ++j) {
     const int m = m_base + j * 16 + (lane & 15);
@@ -52,8 +60,42 @@ __device__ __forceinline__ void store_tile(const GatherConvArgs& a, const f32x4 
         v[3] += ad.w;
       }
       if (a.out_f32) *reinterpret_cast<float4*>(a.out_f32 + o) = make_float4(v[0], v[1], v[2], v[3]);
-      if (a.out_b16)
-        *reinterpret_cast<uint2*>(a.out_b16 + o) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+      const uint2 packed = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+      if (a.out_b16) *reinterpret_cast<uint2*>(a.out_b16 + o) = packed;
+      if (a.stats) {
+        const float r0 = bf16_lo(packed.x), r1 = bf16_hi(packed.x), r2 = bf16_lo(packed.y), r3 = bf16_hi(packed.y);
+        s1[i][0] += r0; s1[i][1] += r1; s1[i][2] += r2; s1[i][3] += r3;
+        s2[i][0] += r0 * r0; s2[i][1] += r1 * r1; s2[i][2] += r2 * r2; s2[i][3] += r3 * r3;
+      }
+    }
+  }
+  if (a.stats) {
+    // Reduce over pixels: first across the 16 lanes that hold the same 4 channels, then across the waves
+    // of the workgroup in LDS, so that the workgroup ends with one global atomic per channel and value.
+    __shared__ float red[2 * BN];
+    __syncthreads();   // the main loop's LDS traffic is over for every wave
+    for (int t = threadIdx.x; t < 2 * BN; t += blockDim.x) red[t] = 0.f;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < FN; ++i)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        float x1 = s1[i][v], x2 = s2[i][v];
+#pragma unroll
+        for (int off = 8; off > 0; off >>= 1) {
+          x1 += __shfl_xor(x1, off, 16);
+          x2 += __shfl_xor(x2, off, 16);
+        }
+        if ((lane & 15) == 0) {
+          const int cl = c_wave + i * 16 + 4 * (lane >> 4) + v;
+          atomicAdd(&red[cl], x1);
+          atomicAdd(&red[BN + cl], x2);
+        }
+      }
+    __syncthreads();
+    for (int t = threadIdx.x; t < 2 * BN; t += blockDim.x) {
+      const int c = c_tile + (t % BN);
+      if (c < a.Co) atomicAdd(a.stats + (t / BN) * a.Co + c, red[t]);
     }
   }
 }

@@ -132,7 +132,7 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(GatherConvArgs a) {
     __syncthreads();
   }
 
-  store_tile<FM, FN>(a, acc, m0 + wave_m * TM, c0 + wave_n * TN, lane);
+  store_tile<FM, FN, BN>(a, acc, m0 + wave_m * TM, c0, wave_n * TN, lane);
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N>
@@ -336,9 +336,9 @@ hipError_t launch_conv_wgrad(const WgradArgs& a, hipStream_t s) {
 // geometry of the three passes of one convolution
 // ------------------------------------------------------------------------------------------------
 hipError_t conv_forward(const ConvShape& c, const bf16_t* x, const bf16_t* w, const float* addend, float* out_f32,
-                        bf16_t* out_b16, hipStream_t s) {
+                        bf16_t* out_b16, float* stats, hipStream_t s) {
   GatherConvArgs a{};
-  a.in = x; a.w = w; a.addend = addend; a.addmask = nullptr; a.out_f32 = out_f32; a.out_b16 = out_b16;
+  a.in = x; a.w = w; a.addend = addend; a.addmask = nullptr; a.out_f32 = out_f32; a.out_b16 = out_b16; a.stats = stats;
   a.N = c.N; a.Hi = c.Hi; a.Wi = c.Wi; a.Ci = c.Cip;
   a.OH = c.Ho(); a.OW = c.Wo(); a.in_stride = c.stride;
   a.OHf = c.Ho(); a.OWf = c.Wo(); a.out_stride = 1; a.ooh = 0; a.oow = 0;

@@ -148,7 +148,7 @@ __global__ __launch_bounds__(256) void conv_gather_dma_kernel(GatherConvArgs a, 
         for (int j = 0; j < FM; ++j) acc[i][j] = mfma16(fa[i], fb[j], acc[i][j]);
     }
   }
-  store_tile<FM, FN>(a, acc, m0 + wave_m * TM, c0 + wave_n * TN, lane);
+  store_tile<FM, FN, BN>(a, acc, m0 + wave_m * TM, c0, wave_n * TN, lane);
 }
 
 bool conv_gather_wide_applies(const GatherConvArgs& a) {

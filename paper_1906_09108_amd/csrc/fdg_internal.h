@@ -25,6 +25,7 @@ struct GatherConvArgs {
   const bf16_t* addmask; // optional: addend counts only where this bf16 tensor (output indexing) is > 0
   float* out_f32;        // optional fp32 output
   bf16_t* out_b16;       // optional bf16 output
+  float* stats;          // optional [2*Co]: += per-channel sum and sum of squares of the bf16-rounded output
   int N, Hi, Wi, Ci;
   int OH, OW, in_stride;
   int OHf, OWf, out_stride, ooh, oow;
@@ -57,8 +58,10 @@ struct ConvShape {
   int Wo() const { return (Wi - 1) / stride + 1; }
 };
 // y[N,Ho,Wo,Co] = conv(x[N,Hi,Wi,Cip], w[Co][T][Cip]) (+ addend)
+// stats (optional, [2*Co], pre-zeroed): += per-channel sum and sum of squares of the bf16-rounded result,
+// i.e. the batch-norm statistics of the tensor just produced
 hipError_t conv_forward(const ConvShape& c, const bf16_t* x, const bf16_t* w, const float* addend, float* out_f32,
-                        bf16_t* out_b16, hipStream_t s);
+                        bf16_t* out_b16, float* stats, hipStream_t s);
 // dx[N,Hi,Wi,Cip] = conv^T(dy[N,Ho,Wo,Co], wt[Cip][T][Co]) (+ addend, optionally only where addmask > 0)
 hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                       const bf16_t* addmask, float* out_f32, bf16_t* out_b16, hipStream_t s);
@@ -140,6 +143,8 @@ struct WeightEmitEntry {
   int32_t Co, T, Ci, Cip;
   uint32_t block_start; // first block of this conv in the launch
 };
+// blocks the snapshot kernel needs for one convolution (64 x 64 tiles per tap)
+inline uint32_t emit_blocks_for(int Co, int Cip, int T) { return (uint32_t)(((Co + 63) / 64) * ((Cip + 63) / 64) * T); }
 hipError_t launch_emit_weights(const float* params, bf16_t* warena, const WeightEmitEntry* table_dev, int nconv,
                                int total_blocks, hipStream_t s);
 

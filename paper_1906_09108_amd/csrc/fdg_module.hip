@@ -227,7 +227,7 @@ bool build_plan(const fdg_module_desc* desc, Plan& p, fdg_status* why) {
   p.small_count = align_up(small, 4);
   p.P = p.small_off + p.small_count;
   if (p.P >= (1ull << 31) || p.warena_elems >= (1ull << 32) || p.maxE >= (1ull << 31)) { *why = FDG_ERR_UNSUPPORTED; return false; }
-  for (const ConvInfo& ci : p.convs) p.emit_blocks += ((size_t)ci.sh.Co * ci.sh.T * ci.sh.Cip + 1023) / 1024;
+  for (const ConvInfo& ci : p.convs) p.emit_blocks += emit_blocks_for(ci.sh.Co, ci.sh.Cip, ci.sh.T);
   // workspace layout
   size_t o = 0;
   auto take = [&](size_t bytes) { const size_t at = o; o += align_up(bytes, kAlign); return at; };
@@ -367,11 +367,11 @@ inline double conv_out_elems(const ConvShape& c) { return (double)c.N * c.Ho() *
 inline double conv_w_elems(const ConvShape& c) { return (double)c.Co * c.T * c.Cip; }
 
 hipError_t mconv_forward(const fdg_module* m, const ConvInfo& c, const bf16_t* x, const bf16_t* w, const float* addend,
-                         float* out_f32, bf16_t* out_b16, hipStream_t s) {
+                         float* out_f32, bf16_t* out_b16, float* stats, hipStream_t s) {
   const double bytes = 2 * conv_in_elems(c.sh) + 2 * conv_w_elems(c.sh) +
                        conv_out_elems(c.sh) * ((addend ? 4 : 0) + (out_f32 ? 4 : 0) + (out_b16 ? 2 : 0));
   ProfScope ps(m, PC_CONV_FWD, conv_flops(c.sh), bytes, s);
-  return conv_forward(c.sh, x, w, addend, out_f32, out_b16, s);
+  return conv_forward(c.sh, x, w, addend, out_f32, out_b16, stats, s);
 }
 hipError_t mconv_dgrad(const fdg_module* m, const ConvInfo& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                        const bf16_t* addmask, float* out_f32, bf16_t* out_b16, hipStream_t s) {
@@ -474,7 +474,7 @@ fdg_status fdg_module_create(const fdg_module_desc* desc, void* dev_workspace, s
       tab[i].src_off = (uint32_t)c.p_off; tab[i].w_off = (uint32_t)c.w_off; tab[i].wt_off = (uint32_t)c.wt_off;
       tab[i].Co = c.sh.Co; tab[i].T = c.sh.T; tab[i].Ci = c.sh.Ci; tab[i].Cip = c.sh.Cip;
       tab[i].block_start = blk;
-      blk += (uint32_t)(((size_t)c.sh.Co * c.sh.T * c.sh.Cip + 1023) / 1024);
+      blk += emit_blocks_for(c.sh.Co, c.sh.Cip, c.sh.T);
     }
     e = hipMemcpyAsync(m->ws + p.o_table, tab.data(), tab.size() * sizeof(WeightEmitEntry), hipMemcpyHostToDevice, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);  // tab is a host temporary
@@ -514,30 +514,28 @@ fdg_status fdg_forward(fdg_module* m, const float* x_dev, const int32_t* labels_
   FDG_TRY(launch_nchw_to_nhwc(x_dev, (p.d.c_in % 8 == 0) ? m->S(cur) : nullptr, v.xin(), N, p.d.c_in, p.d.h_in * p.d.w_in,
                               p.Cp_in, 1.f, s));
   const bf16_t* cur_b = v.xin();
+  bool stats_ready = false;   // the sums of this layer's leading BN were taken by the producer of its input
   for (size_t li = 0; li < p.L.size(); ++li) {
     const LayerPlan& L = p.L[li];
     const int nxt = cur ^ 1;
+    bool next_ready = false;
     if (L.kind == FDG_STEM_CONV_BN_RELU) {
       const ConvInfo& c0 = p.convs[L.conv[0]];
       const BnInfo& b0 = p.bns[L.bn[0]];
-      FDG_TRY(mconv_forward(m, c0, cur_b, v.W(c0), nullptr, nullptr, v.act(L.act[0]), s));
-      FDG_TRY(bn_stats(v, b0, v.act(L.act[0]), s));
+      FDG_TRY(mconv_forward(m, c0, cur_b, v.W(c0), nullptr, nullptr, v.act(L.act[0]), v.sums(b0), s));
       FDG_TRY(bn_apply(m, v, b0, v.act(L.act[0]), nullptr, nullptr, nullptr, m->S(nxt), v.act(L.out_b), s));
     } else if (L.kind == FDG_BASIC_POSTACT) {
       const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]];
       const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]];
       bf16_t *t_c1 = v.act(L.act[0]), *t_a1 = v.act(L.act[1]), *t_c2 = v.act(L.act[2]);
-      FDG_TRY(mconv_forward(m, c1, cur_b, v.W(c1), nullptr, nullptr, t_c1, s));
-      FDG_TRY(bn_stats(v, b1, t_c1, s));
+      FDG_TRY(mconv_forward(m, c1, cur_b, v.W(c1), nullptr, nullptr, t_c1, v.sums(b1), s));
       FDG_TRY(bn_apply(m, v, b1, t_c1, nullptr, nullptr, nullptr, nullptr, t_a1, s));
-      FDG_TRY(mconv_forward(m, c2, t_a1, v.W(c2), nullptr, nullptr, t_c2, s));
-      FDG_TRY(bn_stats(v, b2, t_c2, s));
+      FDG_TRY(mconv_forward(m, c2, t_a1, v.W(c2), nullptr, nullptr, t_c2, v.sums(b2), s));
       if (L.projects) {
         const ConvInfo& cp = p.convs[L.conv[2]];
         const BnInfo& bp = p.bns[L.bn[2]];
         bf16_t* t_p = v.act(L.act[3]);
-        FDG_TRY(mconv_forward(m, cp, cur_b, v.W(cp), nullptr, nullptr, t_p, s));
-        FDG_TRY(bn_stats(v, bp, t_p, s));
+        FDG_TRY(mconv_forward(m, cp, cur_b, v.W(cp), nullptr, nullptr, t_p, v.sums(bp), s));
         FDG_TRY(bn_apply(m, v, b2, t_c2, nullptr, &bp, t_p, m->S(nxt), v.act(L.out_b), s));
       } else {
         FDG_TRY(bn_apply(m, v, b2, t_c2, m->S(cur), nullptr, nullptr, m->S(nxt), v.act(L.out_b), s));
@@ -546,23 +544,27 @@ fdg_status fdg_forward(fdg_module* m, const float* x_dev, const int32_t* labels_
       const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]];
       const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]];
       bf16_t *t_o1 = v.act(L.act[0]), *t_c1 = v.act(L.act[1]), *t_o2 = v.act(L.act[2]);
-      FDG_TRY(bn_stats(v, b1, cur_b, s));
+      if (!stats_ready) FDG_TRY(bn_stats(v, b1, cur_b, s));
       FDG_TRY(bn_apply(m, v, b1, cur_b, nullptr, nullptr, nullptr, nullptr, t_o1, s));
-      FDG_TRY(mconv_forward(m, c1, t_o1, v.W(c1), nullptr, nullptr, t_c1, s));
-      FDG_TRY(bn_stats(v, b2, t_c1, s));
+      FDG_TRY(mconv_forward(m, c1, t_o1, v.W(c1), nullptr, nullptr, t_c1, v.sums(b2), s));
       FDG_TRY(bn_apply(m, v, b2, t_c1, nullptr, nullptr, nullptr, nullptr, t_o2, s));
       const float* shortcut = m->S(cur);
       if (L.projects) {
         const ConvInfo& cp = p.convs[L.conv[2]];
-        FDG_TRY(mconv_forward(m, cp, t_o1, v.W(cp), nullptr, m->TP(), nullptr, s));
+        FDG_TRY(mconv_forward(m, cp, t_o1, v.W(cp), nullptr, m->TP(), nullptr, nullptr, s));
         shortcut = m->TP();
       }
-      FDG_TRY(mconv_forward(m, c2, t_o2, v.W(c2), shortcut, m->S(nxt), v.act(L.out_b), s));
+      // the block output is the next layer's BN input when that layer is pre-activated: take its sums here
+      float* next_stats = nullptr;
+      if (li + 1 < p.L.size() && (p.L[li + 1].kind == FDG_BASIC_PREACT || p.L[li + 1].kind == FDG_HEAD_PREACT))
+        next_stats = v.sums(p.bns[p.L[li + 1].bn[0]]);
+      FDG_TRY(mconv_forward(m, c2, t_o2, v.W(c2), shortcut, m->S(nxt), v.act(L.out_b), next_stats, s));
+      next_ready = next_stats != nullptr;
     } else {  // heads
       const bf16_t* o = cur_b;
       if (L.kind == FDG_HEAD_PREACT) {
         const BnInfo& b0 = p.bns[L.bn[0]];
-        FDG_TRY(bn_stats(v, b0, cur_b, s));
+        if (!stats_ready) FDG_TRY(bn_stats(v, b0, cur_b, s));
         FDG_TRY(bn_apply(m, v, b0, cur_b, nullptr, nullptr, nullptr, nullptr, v.act(L.act[0]), s));
         o = v.act(L.act[0]);
       }
@@ -574,6 +576,7 @@ fdg_status fdg_forward(fdg_module* m, const float* x_dev, const int32_t* labels_
     }
     cur = nxt;
     cur_b = v.act(L.out_b);
+    stats_ready = next_ready;
   }
   if (!p.is_top) FDG_TRY(launch_nhwc_to_nchw(m->S(cur), y_dev, N, p.out_c, p.out_h * p.out_w, p.out_c, s));
   ++m->seq_fwd;

@@ -17,12 +17,12 @@ inline hipStream_t st(void* s) { return static_cast<hipStream_t>(s); }
 
 extern "C" {
 
-int fdgk_conv_fwd(const void* x_b16, const void* w_b16, const float* addend_f32, float* y_f32, void* y_b16, int n,
-                  int h, int w, int ci, int co, int ksize, int stride, void* hip_stream) {
+int fdgk_conv_fwd(const void* x_b16, const void* w_b16, const float* addend_f32, float* y_f32, void* y_b16,
+                  float* stats_f32, int n, int h, int w, int ci, int co, int ksize, int stride, void* hip_stream) {
   ConvShape c;
   if (!x_b16 || !w_b16 || (!y_f32 && !y_b16) || !conv_shape(c, n, h, w, ci, co, ksize, stride)) return (int)hipErrorInvalidValue;
   return (int)conv_forward(c, static_cast<const bf16_t*>(x_b16), static_cast<const bf16_t*>(w_b16), addend_f32, y_f32,
-                           static_cast<bf16_t*>(y_b16), st(hip_stream));
+                           static_cast<bf16_t*>(y_b16), stats_f32, st(hip_stream));
 }
 
 int fdgk_conv_dgrad(const void* dy_b16, const void* wt_b16, const float* addend_f32, const void* addmask_b16,

@@ -31,41 +31,64 @@ __device__ __forceinline__ void store8_f32(float* p, const float (&f)[8]) {
 
 constexpr int kThreads = 256;
 
-// Column reduction helper.  Threads are laid out as (row lane r, channel group cg) with cg fastest;
-// each thread holds NV partial sums for its 8 channels.  Partials of equal cg are added through LDS
-// and the first row lane adds the block result to global memory.
+// Per-channel reductions over the rows of an [M, C] tensor.  A block owns up to 64 channels (CGB groups
+// of 8 channels, CGB in {1,2,4,8}) and a range of rows; thread t handles channel group t % CGB of row lane
+// t / CGB, so a wavefront reads whole 128-byte row segments.  Partials of the row lanes are added
+// through LDS and each block ends with one atomic add per channel and value.
+struct ReduceShape {
+  int CGB, RL, rows_per_block;
+  dim3 grid;
+};
+static ReduceShape reduce_shape(int M, int C) {
+  ReduceShape r;
+  const int CG = C / 8;
+  r.CGB = CG >= 8 ? 8 : (CG >= 4 ? 4 : (CG >= 2 ? 2 : 1));
+  r.RL = kThreads / r.CGB;
+  const int cblocks = (CG + r.CGB - 1) / r.CGB;
+  int rblocks = (1024 + cblocks - 1) / cblocks;                 // about four blocks per compute unit
+  const int max_rblocks = (M + r.RL * 4 - 1) / (r.RL * 4);      // at least four rows per thread
+  if (rblocks > max_rblocks) rblocks = max_rblocks;
+  if (rblocks < 1) rblocks = 1;
+  int rpb = (M + rblocks - 1) / rblocks;
+  rpb = (rpb + r.RL - 1) / r.RL * r.RL;
+  r.rows_per_block = rpb;
+  r.grid = dim3(cblocks, (M + rpb - 1) / rpb, 1);
+  return r;
+}
+
 template <int NV>
-__device__ __forceinline__ void block_reduce_to_global(float (&v)[NV][8], float* const (&dst)[NV], int cg, int r, int CG,
-                                                       int R, float* smem /* [R*CG*8] */) {
+__device__ __forceinline__ void block_reduce_to_global(float (&v)[NV][8], float* const (&dst)[NV], int cgl, int rl, int CGB,
+                                                       int RL, int c_base, int C, float* smem /* [NV][RL][CGB*8] */) {
+  const int W = CGB * 8;
 #pragma unroll
-  for (int q = 0; q < NV; ++q) {
-    __syncthreads();
-    if (cg < CG && r < R) {
+  for (int q = 0; q < NV; ++q)
 #pragma unroll
-      for (int i = 0; i < 8; ++i) smem[(r * CG + cg) * 8 + i] = v[q][i];
-    }
-    __syncthreads();
-    // CG*8 columns, summed over R rows
-    for (int col = threadIdx.x; col < CG * 8; col += blockDim.x) {
-      float s = 0.f;
-      for (int rr = 0; rr < R; ++rr) s += smem[rr * CG * 8 + col];
-      atomicAdd(dst[q] + col, s);
-    }
+    for (int i = 0; i < 8; ++i) smem[(q * RL + rl) * W + cgl * 8 + i] = v[q][i];
+  __syncthreads();
+  for (int t = threadIdx.x; t < NV * W; t += blockDim.x) {
+    const int q = t / W, col = t % W;
+    if (c_base + col >= C) continue;
+    float s = 0.f;
+    for (int rr = 0; rr < RL; ++rr) s += smem[(q * RL + rr) * W + col];
+    atomicAdd(dst[q] + c_base + col, s);
   }
 }
 
 // ---- BN forward statistics: sums[c] += sum x, sums[C + c] += sum x^2 --------------------------------
 __global__ __launch_bounds__(kThreads) void bn_stats_kernel(const bf16_t* __restrict__ x, float* __restrict__ sums, int M,
-                                                            int C, int rows_per_block) {
+                                                            int C, int CGB, int rows_per_block) {
   extern __shared__ float smem[];
-  const int CG = C >> 3, R = kThreads / CG;
-  const int cg = threadIdx.x % CG, r = threadIdx.x / CG;
+  const int RL = kThreads / CGB;
+  const int cgl = threadIdx.x % CGB, rl = threadIdx.x / CGB;
+  const int cg = blockIdx.x * CGB + cgl;
+  const bool cvalid = cg * 8 < C;
   float v[2][8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) v[0][i] = v[1][i] = 0.f;
-  const int row_lo = blockIdx.x * rows_per_block, row_hi = min(M, row_lo + rows_per_block);
-  if (r < R) {
-    for (int row = row_lo + r; row < row_hi; row += R) {
+  const int row_lo = blockIdx.y * rows_per_block, row_hi = min(M, row_lo + rows_per_block);
+  if (cvalid) {
+#pragma unroll 4
+    for (int row = row_lo + rl; row < row_hi; row += RL) {
       float f[8];
       unpack8(*reinterpret_cast<const uint4*>(x + (size_t)row * C + cg * 8), f);
 #pragma unroll
@@ -76,25 +99,14 @@ __global__ __launch_bounds__(kThreads) void bn_stats_kernel(const bf16_t* __rest
     }
   }
   float* const dst[2] = {sums, sums + C};
-  block_reduce_to_global<2>(v, dst, cg, r, CG, R, smem);
-}
-
-static int reduce_grid(int M, int C, int* rows_per_block) {
-  const int CG = C / 8, R = kThreads / CG;
-  int blocks = (M + R * 4 - 1) / (R * 4);  // at least 4 rows per thread
-  if (blocks > 1024) blocks = 1024;
-  if (blocks < 1) blocks = 1;
-  int rpb = (M + blocks - 1) / blocks;
-  rpb = (rpb + R - 1) / R * R;
-  *rows_per_block = rpb;
-  return (M + rpb - 1) / rpb;
+  block_reduce_to_global<2>(v, dst, cgl, rl, CGB, RL, blockIdx.x * CGB * 8, C, smem);
 }
 
 hipError_t launch_bn_stats(const bf16_t* x, float* sums, int M, int C, hipStream_t s) {
   if (C % 8 != 0 || C > 2048 || M <= 0) return hipErrorInvalidValue;
-  int rpb;
-  const int blocks = reduce_grid(M, C, &rpb);
-  hipLaunchKernelGGL(bn_stats_kernel, dim3(blocks), dim3(kThreads), kThreads * 8 * sizeof(float), s, x, sums, M, C, rpb);
+  const ReduceShape r = reduce_shape(M, C);
+  hipLaunchKernelGGL(bn_stats_kernel, r.grid, dim3(kThreads), 2 * kThreads * 8 * sizeof(float), s, x, sums, M, C, r.CGB,
+                     r.rows_per_block);
   return hipGetLastError();
 }
 
@@ -202,28 +214,30 @@ __device__ __forceinline__ void load_masked_dy(const void* dy, const bf16_t* mas
 }
 
 template <bool DY_F32>
-__global__ __launch_bounds__(kThreads) void bn_bwd_reduce_kernel(BnBwdArgs a, int rows_per_block) {
-  extern __shared__ float smem[];  // max(2C, 256*8)
-  const int C = a.C, CG = C >> 3, R = kThreads / CG;
-  const int cg = threadIdx.x % CG, r = threadIdx.x / CG;
-  float* mean = smem;
-  float* is = smem + C;
-  bn_moments(a.sums, C, 1.f / (float)a.M, a.eps, mean, is);
-  __syncthreads();
+__global__ __launch_bounds__(kThreads) void bn_bwd_reduce_kernel(BnBwdArgs a, int CGB, int rows_per_block) {
+  extern __shared__ float smem[];  // 2 * 256 * 8 floats
+  const int C = a.C;
+  const int RL = kThreads / CGB;
+  const int cgl = threadIdx.x % CGB, rl = threadIdx.x / CGB;
+  const int cg = blockIdx.x * CGB + cgl;
+  const bool cvalid = cg * 8 < C;
   float mu[8], iv[8];
-  if (r < R) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      mu[i] = mean[cg * 8 + i];
-      iv[i] = is[cg * 8 + i];
-    }
-  }
   float v[2][8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) v[0][i] = v[1][i] = 0.f;
-  const int row_lo = blockIdx.x * rows_per_block, row_hi = min(a.M, row_lo + rows_per_block);
-  if (r < R) {
-    for (int row = row_lo + r; row < row_hi; row += R) {
+  if (cvalid) {
+    const float invM = 1.f / (float)a.M;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int c = cg * 8 + i;
+      const float m = a.sums[c] * invM;
+      const float var = fmaxf(a.sums[C + c] * invM - m * m, 0.f);
+      mu[i] = m;
+      iv[i] = rsqrtf(var + a.eps);
+    }
+    const int row_lo = blockIdx.y * rows_per_block, row_hi = min(a.M, row_lo + rows_per_block);
+#pragma unroll 2
+    for (int row = row_lo + rl; row < row_hi; row += RL) {
       const size_t o = (size_t)row * C + cg * 8;
       float g[8], xv[8];
       load_masked_dy<DY_F32>(a.dy, a.mask, o, g);
@@ -236,19 +250,17 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_reduce_kernel(BnBwdArgs a, in
     }
   }
   float* const dst[2] = {a.bsums, a.bsums + C};
-  block_reduce_to_global<2>(v, dst, cg, r, CG, R, smem);
+  block_reduce_to_global<2>(v, dst, cgl, rl, CGB, RL, blockIdx.x * CGB * 8, C, smem);
 }
 
 hipError_t launch_bn_bwd_reduce(const BnBwdArgs& a, hipStream_t s) {
   if (a.C % 8 != 0 || a.C > 2048 || a.M <= 0 || !a.mask) return hipErrorInvalidValue;
-  int rpb;
-  const int blocks = reduce_grid(a.M, a.C, &rpb);
-  size_t sm = (size_t)kThreads * 8 * sizeof(float);
-  if (sm < 2 * (size_t)a.C * sizeof(float)) sm = 2 * (size_t)a.C * sizeof(float);
+  const ReduceShape r = reduce_shape(a.M, a.C);
+  const size_t sm = 2 * (size_t)kThreads * 8 * sizeof(float);
   if (a.dy_is_f32)
-    hipLaunchKernelGGL(bn_bwd_reduce_kernel<true>, dim3(blocks), dim3(kThreads), sm, s, a, rpb);
+    hipLaunchKernelGGL(bn_bwd_reduce_kernel<true>, r.grid, dim3(kThreads), sm, s, a, r.CGB, r.rows_per_block);
   else
-    hipLaunchKernelGGL(bn_bwd_reduce_kernel<false>, dim3(blocks), dim3(kThreads), sm, s, a, rpb);
+    hipLaunchKernelGGL(bn_bwd_reduce_kernel<false>, r.grid, dim3(kThreads), sm, s, a, r.CGB, r.rows_per_block);
   return hipGetLastError();
 }
 
@@ -502,28 +514,35 @@ hipError_t launch_sgd(float* theta, float* v, const float* g, size_t count, floa
 }
 
 // ---- bf16 weight snapshot ------------------------------------------------------------------------
-// One block handles 1024 consecutive elements of one convolution's padded [Co][T][Cip] layout.
+// One block converts one 64 (co) x 64 (ci) tile of one filter tap of one convolution: it reads the fp32
+// master [Co][T][Ci] along ci, writes the forward layout [Co][T][Cip] along ci and, after a transpose
+// through LDS, the data-gradient layout [Cip][T][Co] along co, so every access is coalesced.
 __global__ __launch_bounds__(kThreads) void emit_weights_kernel(const float* __restrict__ params, bf16_t* __restrict__ warena,
                                                                 const WeightEmitEntry* __restrict__ table, int nconv) {
-  // find the conv this block belongs to (block_start is ascending)
-  int lo = 0, hi = nconv - 1;
+  __shared__ float tile[64][65];
+  int lo = 0, hi = nconv - 1;   // the conv this block belongs to (block_start is ascending)
   while (lo < hi) {
     const int mid = (lo + hi + 1) >> 1;
     if (table[mid].block_start <= blockIdx.x) lo = mid; else hi = mid - 1;
   }
   const WeightEmitEntry e = table[lo];
-  const int per_co = e.T * e.Cip;
-  const int total = e.Co * per_co;
-  const int base = (blockIdx.x - e.block_start) * 1024;
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int idx = base + q * kThreads + threadIdx.x;
-    if (idx >= total) break;
-    const int co = idx / per_co, rem = idx % per_co, t = rem / e.Cip, ci = rem % e.Cip;
-    const float v = ci < e.Ci ? params[e.src_off + ((size_t)co * e.T + t) * e.Ci + ci] : 0.f;
-    const bf16_t b = (bf16_t)v;
-    warena[e.w_off + idx] = b;
-    warena[e.wt_off + ((size_t)ci * e.T + t) * e.Co + co] = b;
+  const int cit = (e.Cip + 63) / 64, cot = (e.Co + 63) / 64;
+  int local = blockIdx.x - e.block_start;
+  const int ci0 = (local % cit) * 64;
+  local /= cit;
+  const int co0 = (local % cot) * 64, t = local / cot;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int r = ty; r < 64; r += 4) {
+    const int co = co0 + r, ci = ci0 + tx;
+    float v = 0.f;
+    if (co < e.Co && ci < e.Ci) v = params[e.src_off + ((size_t)co * e.T + t) * e.Ci + ci];
+    tile[r][tx] = v;
+    if (co < e.Co && ci < e.Cip) warena[e.w_off + ((size_t)co * e.T + t) * e.Cip + ci] = (bf16_t)v;
+  }
+  __syncthreads();
+  for (int r = ty; r < 64; r += 4) {
+    const int ci = ci0 + r, co = co0 + tx;
+    if (ci < e.Cip && co < e.Co) warena[e.wt_off + ((size_t)ci * e.T + t) * e.Co + co] = (bf16_t)tile[tx][r];
   }
 }
 hipError_t launch_emit_weights(const float* params, bf16_t* warena, const WeightEmitEntry* table_dev, int nconv,

@@ -16,7 +16,7 @@ def _lib():
     lib = load()
     if not _ready:
         vp, i, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
-        lib.fdgk_conv_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
+        lib.fdgk_conv_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
         lib.fdgk_conv_dgrad.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
         lib.fdgk_conv_wgrad.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, vp]
         lib.fdgk_bn_stats.argtypes = [vp, vp, i, i, vp]
@@ -34,9 +34,9 @@ def _ok(rc: int, name: str) -> None:
         raise RuntimeError(f"{name} failed with hipError_t {rc}")
 
 
-def fdgk_conv_fwd(x_b16, w_b16, addend_f32, y_f32, y_b16, n, h, w, ci, co, ksize, stride, stream=None):
-    _ok(_lib().fdgk_conv_fwd(_ptr(x_b16), _ptr(w_b16), _ptr(addend_f32), _ptr(y_f32), _ptr(y_b16), n, h, w, ci, co,
-                             ksize, stride, _stream_handle(stream)), "fdgk_conv_fwd")
+def fdgk_conv_fwd(x_b16, w_b16, addend_f32, y_f32, y_b16, stats_f32, n, h, w, ci, co, ksize, stride, stream=None):
+    _ok(_lib().fdgk_conv_fwd(_ptr(x_b16), _ptr(w_b16), _ptr(addend_f32), _ptr(y_f32), _ptr(y_b16), _ptr(stats_f32),
+                             n, h, w, ci, co, ksize, stride, _stream_handle(stream)), "fdgk_conv_fwd")
 
 
 def fdgk_conv_dgrad(dy_b16, wt_b16, addend_f32, addmask_b16, dx_f32, dx_b16, n, h, w, ci, co, ksize, stride, stream=None):

@@ -99,11 +99,17 @@ def test_conv_fwd(case):
     add = np.random.default_rng(2).standard_normal(ref.shape).astype(np.float32)
     y32 = t.full((n, ho, wo, co), float("nan"), dtype=t.float32, device="cuda")
     y16 = t.zeros((n, ho, wo, co), dtype=t.bfloat16, device="cuda")
-    K.fdgk_conv_fwd(xd, wd, None, y32, y16, n, h, w, ci, co, k, s)
+    stats = t.zeros(2 * co, dtype=t.float32, device="cuda")
+    K.fdgk_conv_fwd(xd, wd, None, y32, y16, stats, n, h, w, ci, co, k, s)
     t.cuda.synchronize()
     assert rel(nhwc_to_nchw(y32), ref) <= F32_TOL
     assert rel(nhwc_to_nchw(y16), ref) <= B16_TOL
-    K.fdgk_conv_fwd(xd, wd, to_dev_nhwc_f32(add), y32, None, n, h, w, ci, co, k, s)
+    # fused batch-norm statistics: sums of the bf16 values just written
+    yb = y16.to(t.float64).reshape(-1, co)
+    got = stats.cpu().numpy().astype(np.float64)
+    assert rel(got[:co], yb.sum(0).cpu().numpy()) <= 1e-5
+    assert rel(got[co:], (yb * yb).sum(0).cpu().numpy()) <= 1e-5
+    K.fdgk_conv_fwd(xd, wd, to_dev_nhwc_f32(add), y32, None, None, n, h, w, ci, co, k, s)
     t.cuda.synchronize()
     assert rel(nhwc_to_nchw(y32), ref + add) <= F32_TOL
 
