@@ -398,9 +398,16 @@ hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, co
   return hipSuccess;
 }
 
-hipError_t conv_wgrad(const ConvShape& c, const bf16_t* x, const bf16_t* dy, float* dw, hipStream_t s) {
+size_t conv_wgrad_scratch_bytes(const ConvShape& c) {
   WgradArgs a{};
-  a.dy = dy; a.x = x; a.dw = dw;
+  a.Co = c.Co; a.Ci = c.Ci; a.Cx = c.Cip; a.OW = c.Wo(); a.ntaps = c.T;
+  return conv_wgrad_wide_applies(a) ? (size_t)8 * c.Co * c.T * c.Ci * 4 : 0;
+}
+
+hipError_t conv_wgrad(const ConvShape& c, const bf16_t* x, const bf16_t* dy, float* dw, float* scratch,
+                      size_t scratch_bytes, hipStream_t s) {
+  WgradArgs a{};
+  a.dy = dy; a.x = x; a.dw = dw; a.scratch = scratch; a.scratch_bytes = scratch_bytes;
   a.N = c.N; a.OH = c.Ho(); a.OW = c.Wo(); a.Co = c.Co;
   a.Hi = c.Hi; a.Wi = c.Wi; a.Cx = c.Cip; a.Ci = c.Ci;
   a.stride = c.stride; a.ntaps = c.T;

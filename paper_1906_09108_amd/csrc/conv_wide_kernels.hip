@@ -12,8 +12,6 @@
 //     workgroups for the 8x8 and 16x16 stages, i.e. whole rounds of the 256 compute units;
 //   * workgroups are numbered so that the eight XCDs (workgroup id mod 8) each own a contiguous range of
 //     pixel tiles with all of their channel tiles, keeping operand reuse inside one L2.
-#include <cstdlib>
-
 #include "conv_common.h"
 
 namespace fdg {
@@ -204,6 +202,8 @@ __device__ __forceinline__ bf16x8 lds_read_tr8(const unsigned char* p) {
 
 struct WgradWideLaunch {
   int co_tiles, ci_tiles, splits, chunks_per_split;
+  float* partial;        // when set: split s stores its block at partial + s * split_stride (no atomics)
+  size_t split_stride;   // elements of one [Co][T][Ci] array
 };
 
 template <int STAGES>
@@ -341,9 +341,25 @@ __global__ __launch_bounds__(256) void conv_wgrad_dma_kernel(WgradArgs a, WgradW
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
         const int co = co0 + wm * 80 + i * 16 + 4 * (lane >> 4) + v;
-        if (co < a.Co) atomicAdd(a.dw + ((size_t)co * a.ntaps + tapi) * a.Ci + ci, acc[i][j][v]);
+        if (co >= a.Co) continue;
+        const size_t o = ((size_t)co * a.ntaps + tapi) * a.Ci + ci;
+        if (L.partial) L.partial[(size_t)split * L.split_stride + o] = acc[i][j][v];
+        else atomicAdd(a.dw + o, acc[i][j][v]);
       }
     }
+}
+
+// dw += sum over splits of the partial arrays
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(float4* __restrict__ dw, const float4* __restrict__ partial,
+                                                           size_t n4, int splits, size_t stride4) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
+    float4 s = dw[i];
+    for (int k = 0; k < splits; ++k) {
+      const float4 p = partial[(size_t)k * stride4 + i];
+      s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+    }
+    dw[i] = s;
+  }
 }
 
 bool conv_wgrad_wide_applies(const WgradArgs& a) {
@@ -367,13 +383,38 @@ hipError_t launch_conv_wgrad_wide(const WgradArgs& a, hipStream_t s) {
   L.ci_tiles = a.Ci / 160;
   const int tiles = L.co_tiles * L.ci_tiles * a.ntaps;
   const int total_chunks = (Mtot + 63) / 64;
-  static const int target_wgs = [] { const char* e = getenv("FDG_WGRAD_WGS"); return e ? atoi(e) : 512; }();
-  int splits = target_wgs / tiles;                 // about two rounds of the 256 compute units (more splits = more atomics)
-  if (splits > total_chunks / 4) splits = total_chunks / 4;
-  if (splits < 1) splits = 1;
-  L.chunks_per_split = (total_chunks + splits - 1) / splits;
+  const size_t elems = (size_t)a.Co * a.ntaps * a.Ci;
+  // Number of pixel splits.  With scratch memory each split stores its partial block and a second kernel
+  // adds them (cost: the partials are written and read once); without it the splits add with atomics, which
+  // cost more the more splits there are.  Model: rounds of 256 workgroups x chunks per split x ~1 us, plus the
+  // partial traffic at ~3 TB/s.
+  const int max_by_scratch = a.scratch ? (int)(a.scratch_bytes / (elems * 4)) : 0;
+  int best = 1;
+  if (max_by_scratch >= 2) {
+    double best_cost = 1e30;
+    for (int S = 1; S <= 8 && S <= max_by_scratch && S <= total_chunks; ++S) {
+      const int rounds = (tiles * S + 255) / 256, cps = (total_chunks + S - 1) / S;
+      const double cost = (double)rounds * cps * 1.0 + (S > 1 ? (2.0 * S + 2.0) * elems * 4 / 3.0e6 : 0.0);
+      if (cost < best_cost) { best_cost = cost; best = S; }
+    }
+  } else {
+    best = 512 / tiles;   // atomics: about two rounds of workgroups
+    if (best > total_chunks / 4) best = total_chunks / 4;
+    if (best < 1) best = 1;
+  }
+  L.chunks_per_split = (total_chunks + best - 1) / best;
   L.splits = (total_chunks + L.chunks_per_split - 1) / L.chunks_per_split;
+  const bool use_partial = max_by_scratch >= 2 && L.splits > 1;
+  L.partial = use_partial ? a.scratch : nullptr;
+  L.split_stride = elems;
   hipLaunchKernelGGL((conv_wgrad_dma_kernel<STAGES>), dim3(tiles * L.splits), dim3(256), lds, s, a, L);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || !use_partial) return e;
+  const size_t n4 = elems / 4;   // Ci % 160 == 0, so a multiple of 4
+  size_t blocks = (n4 + 255) / 256;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, s, reinterpret_cast<float4*>(a.dw),
+                     reinterpret_cast<const float4*>(a.scratch), n4, L.splits, elems / 4);
   return hipGetLastError();
 }
 

@@ -47,6 +47,8 @@ struct WgradArgs {
   int stride;
   int ntaps;
   int tap[9];        // pack_tap(dh, dw, 0)
+  float* scratch;    // optional device scratch for split partial sums (see conv_wgrad_scratch_bytes)
+  size_t scratch_bytes;
 };
 hipError_t launch_conv_wgrad(const WgradArgs& a, hipStream_t s);
 
@@ -66,7 +68,11 @@ hipError_t conv_forward(const ConvShape& c, const bf16_t* x, const bf16_t* w, co
 hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                       const bf16_t* addmask, float* out_f32, bf16_t* out_b16, hipStream_t s);
 // dw[Co][T][Ci] += sum over pixels of dy * x   (fp32 atomics)
-hipError_t conv_wgrad(const ConvShape& c, const bf16_t* x, const bf16_t* dy, float* dw, hipStream_t s);
+// scratch (optional): device memory for the partial sums of the pixel splits; without it they are added
+// with atomics.  conv_wgrad_scratch_bytes gives the useful size for a shape (0: the shape never uses it).
+hipError_t conv_wgrad(const ConvShape& c, const bf16_t* x, const bf16_t* dy, float* dw, float* scratch,
+                      size_t scratch_bytes, hipStream_t s);
+size_t conv_wgrad_scratch_bytes(const ConvShape& c);
 
 // Batch-norm pieces on [M, C] NHWC tensors (C % 8 == 0, C <= 2048).
 // sums = [sum_c | sumsq_c] fp32, pre-zeroed; accumulated with atomics.

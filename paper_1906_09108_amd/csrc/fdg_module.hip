@@ -2,6 +2,7 @@
 // forwards, and the launch sequences of forward / delayed backward / update (Section III-A, Eq. 10,
 // Eq. 11 and Eq. 15 of arXiv 1906.09108).  This file holds no arithmetic: every number is produced
 // by the kernels in conv_kernels.hip and stream_kernels.hip.
+#include <algorithm>
 #include <cstdio>
 #include <new>
 #include <vector>
@@ -65,6 +66,7 @@ struct Plan {
   size_t o_params = 0, o_mom = 0, o_grads = 0, o_bsums = 0, o_running = 0, o_table = 0, o_slots = 0, slot_bytes = 0;
   size_t s_warena = 0, s_small = 0, s_sums = 0, s_xin = 0, s_acts = 0, s_pooled = 0, s_dl = 0, s_logits = 0, s_labels = 0;
   size_t o_S[2] = {0, 0}, o_G[2] = {0, 0}, o_GB[2] = {0, 0}, o_T[2] = {0, 0}, o_TP = 0, o_dp = 0;
+  size_t o_wscratch = 0, wscratch_bytes = 0;   // partial sums of the split weight gradient
   size_t total = 0;
 };
 
@@ -260,6 +262,8 @@ bool build_plan(const fdg_module_desc* desc, Plan& p, fdg_status* why) {
   for (int i = 0; i < 2; ++i) p.o_T[i] = take(p.maxE * 2);
   p.o_TP = take(p.maxE * 4);
   p.o_dp = take(p.is_top ? (size_t)N * p.head_C * 4 : 0);
+  for (const ConvInfo& ci : p.convs) p.wscratch_bytes = std::max(p.wscratch_bytes, conv_wgrad_scratch_bytes(ci.sh));
+  p.o_wscratch = take(p.wscratch_bytes);
   p.total = o;
   *why = FDG_OK;
   return true;
@@ -383,7 +387,8 @@ hipError_t mconv_dgrad(const fdg_module* m, const ConvInfo& c, const bf16_t* dy,
 hipError_t mconv_wgrad(const fdg_module* m, const ConvInfo& c, const bf16_t* x, const bf16_t* dy, hipStream_t s) {
   const double bytes = 2 * conv_in_elems(c.sh) + 2 * conv_out_elems(c.sh) + 4.0 * c.sh.Co * c.sh.T * c.sh.Ci;
   ProfScope ps(m, PC_CONV_WGRAD, conv_flops(c.sh), bytes, s);
-  return conv_wgrad(c.sh, x, dy, m->grads() + c.p_off, s);
+  return conv_wgrad(c.sh, x, dy, m->grads() + c.p_off, reinterpret_cast<float*>(m->ws + m->p.o_wscratch),
+                    m->p.wscratch_bytes, s);
 }
 
 hipError_t bn_stats(const SlotView& v, const BnInfo& b, const bf16_t* x, hipStream_t s) {

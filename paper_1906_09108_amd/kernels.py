@@ -6,7 +6,7 @@ import ctypes
 
 from .binding import _ptr, _stream_handle, load
 
-KERNEL_EXPORTS = ["fdgk_conv_fwd", "fdgk_conv_dgrad", "fdgk_conv_wgrad", "fdgk_bn_stats", "fdgk_bn_apply",
+KERNEL_EXPORTS = ["fdgk_conv_fwd", "fdgk_conv_dgrad", "fdgk_conv_wgrad", "fdgk_conv_wgrad_scratch_bytes", "fdgk_bn_stats", "fdgk_bn_apply",
                   "fdgk_bn_bwd", "fdgk_sgd"]
 _ready = False
 
@@ -18,13 +18,15 @@ def _lib():
         vp, i, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
         lib.fdgk_conv_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
         lib.fdgk_conv_dgrad.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
-        lib.fdgk_conv_wgrad.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, vp]
+        lib.fdgk_conv_wgrad.argtypes = [vp, vp, vp, vp, sz, i, i, i, i, i, i, i, vp]
+        lib.fdgk_conv_wgrad_scratch_bytes.argtypes = [i, i, i, i, i, i, i]
         lib.fdgk_bn_stats.argtypes = [vp, vp, i, i, vp]
         lib.fdgk_bn_apply.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, f, i, vp]
         lib.fdgk_bn_bwd.argtypes = [vp, i, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, f, vp]
         lib.fdgk_sgd.argtypes = [vp, vp, vp, sz, f, f, f, vp]
         for n in KERNEL_EXPORTS:
             getattr(lib, n).restype = i
+        lib.fdgk_conv_wgrad_scratch_bytes.restype = sz
         _ready = True
     return lib
 
@@ -44,9 +46,15 @@ def fdgk_conv_dgrad(dy_b16, wt_b16, addend_f32, addmask_b16, dx_f32, dx_b16, n, 
                                _ptr(dx_b16), n, h, w, ci, co, ksize, stride, _stream_handle(stream)), "fdgk_conv_dgrad")
 
 
-def fdgk_conv_wgrad(x_b16, dy_b16, dw_f32, n, h, w, ci, co, ksize, stride, stream=None):
-    _ok(_lib().fdgk_conv_wgrad(_ptr(x_b16), _ptr(dy_b16), _ptr(dw_f32), n, h, w, ci, co, ksize, stride,
-                               _stream_handle(stream)), "fdgk_conv_wgrad")
+def fdgk_conv_wgrad_scratch_bytes(n, h, w, ci, co, ksize, stride) -> int:
+    return int(_lib().fdgk_conv_wgrad_scratch_bytes(n, h, w, ci, co, ksize, stride))
+
+
+def fdgk_conv_wgrad(x_b16, dy_b16, dw_f32, scratch_f32, n, h, w, ci, co, ksize, stride, stream=None):
+    """scratch_f32: a float32 CUDA tensor (any contents) or None."""
+    nbytes = 0 if scratch_f32 is None else scratch_f32.numel() * scratch_f32.element_size()
+    _ok(_lib().fdgk_conv_wgrad(_ptr(x_b16), _ptr(dy_b16), _ptr(dw_f32), _ptr(scratch_f32), nbytes, n, h, w, ci, co,
+                               ksize, stride, _stream_handle(stream)), "fdgk_conv_wgrad")
 
 
 def fdgk_bn_stats(x_b16, sums_f32, m, c, stream=None):

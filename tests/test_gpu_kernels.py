@@ -155,11 +155,20 @@ def test_conv_wgrad(case):
     x, wt, dy, ho, wo = _conv_data(case, 5)
     cip = (ci + 7) // 8 * 8
     ref = K32.conv_bwd_weight(x, dy, k, s, 1 if k == 3 else 0).astype(np.float64)   # [co, ci, k, k]
+    xd, dyd = to_dev_nhwc_b16(x, cip), to_dev_nhwc_b16(dy)
     dw = t.zeros((co, k * k, ci), dtype=t.float32, device="cuda")
-    K.fdgk_conv_wgrad(to_dev_nhwc_b16(x, cip), to_dev_nhwc_b16(dy), dw, n, h, w, ci, co, k, s)
+    K.fdgk_conv_wgrad(xd, dyd, dw, None, n, h, w, ci, co, k, s)                     # splits added with atomics
     t.cuda.synchronize()
     got = dw.cpu().numpy().reshape(co, k, k, ci).transpose(0, 3, 1, 2)
     assert rel(got, ref) <= F32_TOL
+    nbytes = K.fdgk_conv_wgrad_scratch_bytes(n, h, w, ci, co, k, s)
+    if nbytes:                                                                      # splits through scratch
+        scratch = t.full((nbytes // 4,), float("nan"), dtype=t.float32, device="cuda")
+        dw2 = t.ones((co, k * k, ci), dtype=t.float32, device="cuda")               # the result is ADDED to dw
+        K.fdgk_conv_wgrad(xd, dyd, dw2, scratch, n, h, w, ci, co, k, s)
+        t.cuda.synchronize()
+        got = dw2.cpu().numpy().reshape(co, k, k, ci).transpose(0, 3, 1, 2) - 1.0
+        assert rel(got, ref) <= F32_TOL
 
 
 BN_CASES = [(189, 16), (4096, 16), (1000, 40), (512, 640), (16384, 32), (77, 2048)]
