@@ -13,6 +13,9 @@
 //   * workgroups are numbered so that the eight XCDs (workgroup id mod 8) each own a contiguous range of
 //     pixel tiles with all of their channel tiles, keeping operand reuse inside one L2.
 #include "conv_common.h"
+#include <stdlib.h>
+#include <type_traits>
+#include <utility>
 
 namespace fdg {
 
@@ -29,23 +32,26 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 0xf) | ((N >> 4) << 14) | (0x7 << 4) | (0xf << 8));
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES>
+// Four waves: wave_m = wave & 1 owns 64 of the tile's 128 pixels and ALL of its BN channels as 2 x (BN/32)
+// accumulator blocks of 32x32; wk = wave >> 1 takes one 32-channel half of every 64-channel k-chunk.  So a
+// wave reads 2 + BN/32 operand fragments for every 2 * BN/32 MFMAs (the best ratio four waves can get on a
+// 128 x 160 tile) and the two k-halves are added once, through LDS, after the main loop.
+template <int BN, int STAGES>
 __global__ __launch_bounds__(256) void conv_gather_dma_kernel(GatherConvArgs a, int m_tiles, int n_tiles) {
-  static_assert(WM * WN == 4, "four waves");
-  static_assert(BM % 32 == 0 && BN % 32 == 0, "row groups of 8 per wave instruction");
+  constexpr int BM = 128;
+  static_assert(BN % 32 == 0, "whole 32x32 blocks");
   constexpr int ROWB = 128;                 // bytes per LDS row = 64 bf16 of one tap
   constexpr int R = BM + BN;
   constexpr int JX = BM / 32, JW = BN / 32; // DMA instructions per thread per chunk: pixel rows, weight rows
   constexpr int NJ = JX + JW;
-  constexpr int TM = BM / WM, TN = BN / WN;
-  constexpr int FM = TM / 16, FN = TN / 16;
-  static_assert(TM % 16 == 0 && TN % 16 == 0, "whole MFMA blocks per wave");
+  constexpr int FM = 2, FN = BN / 32;
   static_assert((STAGES - 2) * NJ < 64, "vmcnt range");
+  static_assert((size_t)STAGES * R * ROWB >= (size_t)2 * FN * FM * 16 * 64 * 4, "room to park the partial sums");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // STAGES * R * ROWB
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: it selects DMA destinations
-  const int wave_m = wave % WM, wave_n = wave / WM;
+  const int wave_m = wave & 1, wk = wave >> 1;
   const int Mtot = a.N * a.OH * a.OW;
 
   // workgroup -> tile, XCD aware: hardware deals workgroup ids round robin over 8 XCDs
@@ -103,18 +109,20 @@ __global__ __launch_bounds__(256) void conv_gather_dma_kernel(GatherConvArgs a, 
     }
   };
 
-  f32x4 acc[FN][FM];
+  f32x16 acc[FN][FM];
 #pragma unroll
   for (int i = 0; i < FN; ++i)
 #pragma unroll
-    for (int j = 0; j < FM; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < FM; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // LDS byte offsets of this lane's operand rows (unit swizzle applied per k-step below)
+  // LDS rows of this lane's operand fragments (unit swizzle applied per k-step below)
   int xrow[FM], wrow[FN];
 #pragma unroll
-  for (int f = 0; f < FM; ++f) xrow[f] = wave_m * TM + f * 16 + (lane & 15);
+  for (int f = 0; f < FM; ++f) xrow[f] = wave_m * 64 + f * 32 + (lane & 31);
 #pragma unroll
-  for (int f = 0; f < FN; ++f) wrow[f] = BM + wave_n * TN + f * 16 + (lane & 15);
+  for (int f = 0; f < FN; ++f) wrow[f] = BM + f * 32 + (lane & 31);
 
 #pragma unroll
   for (int p = 0; p < STAGES - 1; ++p)
@@ -131,8 +139,8 @@ __global__ __launch_bounds__(256) void conv_gather_dma_kernel(GatherConvArgs a, 
     if (kc + STAGES - 1 < nchunks) issue(kc + STAGES - 1);   // overwrites the buffer of chunk kc-1
     const unsigned char* stage = smem + (size_t)(kc % STAGES) * (R * ROWB);
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      const int u = ks * 4 + (lane >> 4);
+    for (int ss = 0; ss < 2; ++ss) {        // the two 16-channel steps of this wave's half chunk
+      const int u = 4 * wk + 2 * ss + (lane >> 5);
       bf16x8 fa[FN], fb[FM];
 #pragma unroll
       for (int f = 0; f < FN; ++f)
@@ -143,39 +151,309 @@ __global__ __launch_bounds__(256) void conv_gather_dma_kernel(GatherConvArgs a, 
 #pragma unroll
       for (int i = 0; i < FN; ++i)
 #pragma unroll
-        for (int j = 0; j < FM; ++j) acc[i][j] = mfma16(fa[i], fb[j], acc[i][j]);
+        for (int j = 0; j < FM; ++j) acc[i][j] = mfma32(fa[i], fb[j], acc[i][j]);
     }
   }
-  store_tile<FM, FN, BN>(a, acc, m0 + wave_m * TM, c0, wave_n * TN, lane);
+  // add the two k-halves: waves 2, 3 park their sums in LDS, waves 0, 1 pick them up
+  wait_vmcnt<0>();
+  __syncthreads();
+  {
+    f32x4* park = reinterpret_cast<f32x4*>(smem) + (size_t)wave_m * (FN * FM * 4 * 64);
+    if (wk == 1) {
+#pragma unroll
+      for (int i = 0; i < FN; ++i)
+#pragma unroll
+        for (int j = 0; j < FM; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+            park[((i * FM + j) * 4 + g) * 64 + lane] =
+                f32x4{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+    }
+    __syncthreads();
+    if (wk == 0) {
+#pragma unroll
+      for (int i = 0; i < FN; ++i)
+#pragma unroll
+        for (int j = 0; j < FM; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const f32x4 p = park[((i * FM + j) * 4 + g) * 64 + lane];
+            acc[i][j][4 * g] += p[0]; acc[i][j][4 * g + 1] += p[1]; acc[i][j][4 * g + 2] += p[2]; acc[i][j][4 * g + 3] += p[3];
+          }
+    }
+  }
+  store_tile32<FM, FN, BN>(a, acc, m0 + wave_m * 64, c0, 0, lane, wk == 0);
+}
+
+// ------------------------------------------------------------------------------------------------
+// 3x3, stride 1, padding 1 (forward and stride-1 data gradient of the wide layers): patch form.
+// ------------------------------------------------------------------------------------------------
+// The nine taps of such a convolution read the same input pixels, shifted.  A tile of 128 consecutive output
+// pixels m0 .. m0+127 (linear in n, oh, ow; input and output grids coincide) only ever touches the input
+// pixels m0 - W - 1 .. m0 + 128 + W, so for each 64-channel block that range ("patch", PR rows) is landed in
+// LDS ONCE and the taps address it with a per-lane row shift; only the weights stream per tap.  Against the
+// generic wide kernel this moves 1.6x fewer bytes from L2 to LDS and, with the patch double buffered per
+// channel block and the weights WS stages deep, looks nine taps (patch) and WS-1 taps (weights) ahead, which
+// covers an L2 miss.  A tap that falls outside the image reads a zero region of LDS instead.
+//
+// Order of the direct-to-LDS loads in every wave: patch(0), w(0..WS-2), then at step i = 9c + t (after the
+// barrier): w(i+WS-1) and, when t == 0, patch(c+1).  Loads complete in order, so "w(i) has landed" is
+// vmcnt <= (WS-2)*JW, plus JX when patch(c+1) was issued after w(i), i.e. for 1 <= t <= WS-1.
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+template <int BN, int PR, int WS>
+__global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m_tiles, int n_tiles) {
+  constexpr int BM = 128, ROWB = 128;
+  static_assert(BN % 32 == 0 && PR % 32 == 0, "whole DMA instructions and 32x32 blocks");
+  constexpr int JX = PR / 32, JW = BN / 32;
+  constexpr int FM = 2, FN = BN / 32;
+  constexpr int XBYTES = PR * ROWB, WBYTES = BN * ROWB;
+  constexpr int ZOFF = 2 * XBYTES + WS * WBYTES;   // 256 bytes of zeros
+  static_assert((WS - 2) * JW + JX < 64, "vmcnt range");
+  static_assert(WS >= 3 && WS <= 9, "pipeline depth");
+  static_assert((size_t)ZOFF >= (size_t)2 * FN * FM * 16 * 64 * 4, "room to park the partial sums");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // ZOFF + 256
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave_m = wave & 1, wk = wave >> 1;
+  const int Mtot = a.N * a.OH * a.OW;
+  const int W = a.Wi, H = a.Hi;
+
+  int t = blockIdx.x;
+  const int total = m_tiles * n_tiles;
+  if ((total & 7) == 0) t = (blockIdx.x & 7) * (total >> 3) + (blockIdx.x >> 3);
+  const int m0 = (t / n_tiles) * BM, c0 = (t % n_tiles) * BN;
+
+  if (tid < 16) reinterpret_cast<uint4*>(smem + ZOFF)[tid] = make_uint4(0u, 0u, 0u, 0u);   // visible after the first barrier
+
+  // ---- per-thread DMA sources ----
+  const char* zero = reinterpret_cast<const char*>(g_zero_word);
+  const char* xsrc[JX];   // this thread's 16 bytes of patch row p at channel block 0, or null
+  const char* wsrc[JW];   // this thread's 16 bytes of weight row at k = 0, or null
+#pragma unroll
+  for (int j = 0; j < JX; ++j) {
+    const int p = 8 * (4 * j + wave) + (lane >> 3);
+    const int u = (lane & 7) ^ ((p >> 1) & 7);
+    const int q = m0 - W - 1 + p;
+    xsrc[j] = (q >= 0 && q < Mtot) ? reinterpret_cast<const char*>(a.in) + (size_t)q * a.Ci * 2 + u * 16 : nullptr;
+  }
+#pragma unroll
+  for (int j = 0; j < JW; ++j) {
+    const int row = 8 * (4 * j + wave) + (lane >> 3);
+    const int u = (lane & 7) ^ ((row >> 1) & 7);
+    const int c = c0 + row;
+    wsrc[j] = c < a.w_rows ? reinterpret_cast<const char*>(a.w) + (size_t)c * a.Kw * 2 + u * 16 : nullptr;
+  }
+  int tdh[9], tdw[9], tko[9];
+#pragma unroll
+  for (int i = 0; i < 9; ++i) {
+    const int tp = a.tap[i];
+    tdh[i] = (tp & 0xff) - 8;
+    tdw[i] = ((tp >> 8) & 0xff) - 8;
+    tko[i] = (tp >> 16) * a.Ci * 2;   // byte offset of the tap's k block in a weight row
+  }
+  const int cpc = a.Ci >> 6;   // channel blocks
+
+  auto issue_x = [&](int c) {
+    unsigned char* stage = smem + (c & 1) * XBYTES;
+    const int cb = c * 128;
+#pragma unroll
+    for (int j = 0; j < JX; ++j) dma16(xsrc[j] ? xsrc[j] + cb : zero, stage + (8 * (4 * j + wave)) * ROWB);
+  };
+  auto issue_w = [&](int slot, int kbyte) {
+    unsigned char* stage = smem + 2 * XBYTES + slot * WBYTES;
+#pragma unroll
+    for (int j = 0; j < JW; ++j) dma16(wsrc[j] ? wsrc[j] + kbyte : zero, stage + (8 * (4 * j + wave)) * ROWB);
+  };
+
+  f32x16 acc[FN][FM];
+#pragma unroll
+  for (int i = 0; i < FN; ++i)
+#pragma unroll
+    for (int j = 0; j < FM; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // this lane's pixels (operand B columns) and weight rows (operand A rows)
+  int prow[FM], poh[FM], pow_[FM];
+#pragma unroll
+  for (int f = 0; f < FM; ++f) {
+    const int r = wave_m * 64 + f * 32 + (lane & 31);
+    const int m = m0 + r;
+    prow[f] = r + W + 1;
+    if (m < Mtot) {
+      pow_[f] = m % a.OW;
+      poh[f] = (m / a.OW) % a.OH;
+    } else {
+      pow_[f] = poh[f] = -4;   // every tap falls outside
+    }
+  }
+  int wrow_off[FN], wrow_swz[FN];
+#pragma unroll
+  for (int f = 0; f < FN; ++f) {
+    const int row = f * 32 + (lane & 31);
+    wrow_off[f] = row * ROWB;
+    wrow_swz[f] = (row >> 1) & 7;
+  }
+
+  issue_x(0);
+#pragma unroll
+  for (int p = 0; p < WS - 1; ++p) issue_w(p, tko[p]);   // 9 taps >= WS - 1 steps always exist
+
+  int slot = 0;   // weight stage of the current step
+  auto chunk_body = [&](int c, auto last_tag) {
+    constexpr bool LAST = decltype(last_tag)::value;
+    const unsigned char* xstage = smem + (c & 1) * XBYTES;
+    static_for<9>([&](auto t_tag) {
+      constexpr int T = decltype(t_tag)::value;
+      constexpr int AHEAD = LAST ? ((8 - T) < (WS - 2) ? (8 - T) : (WS - 2)) : (WS - 2);
+      constexpr int XPEND = (!LAST && T >= 1 && T <= WS - 1) ? JX : 0;
+      wait_vmcnt<AHEAD * JW + XPEND>();
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      constexpr int TT = T + WS - 1;                // tap of the step issued now
+      if constexpr (TT < 9) {
+        issue_w(slot == 0 ? WS - 1 : slot - 1, tko[TT] + c * 128);
+      } else if constexpr (!LAST) {
+        issue_w(slot == 0 ? WS - 1 : slot - 1, tko[TT - 9] + (c + 1) * 128);
+      }
+      if constexpr (T == 0 && !LAST) issue_x(c + 1);
+
+      const unsigned char* wstage = smem + 2 * XBYTES + slot * WBYTES;
+      // patch rows of this tap, or the zero region (same bank position, so it never adds a conflict)
+      int xoff[FM], xswz[FM];
+#pragma unroll
+      for (int f = 0; f < FM; ++f) {
+        const int p = prow[f] + tdh[T] * W + tdw[T];
+        const bool ok = (unsigned)(poh[f] + tdh[T]) < (unsigned)H && (unsigned)(pow_[f] + tdw[T]) < (unsigned)W;
+        xswz[f] = (p >> 1) & 7;
+        xoff[f] = ok ? (int)(xstage - smem) + p * ROWB : ZOFF + (p & 1) * ROWB;
+      }
+#pragma unroll
+      for (int ss = 0; ss < 2; ++ss) {
+        const int u = 4 * wk + 2 * ss + (lane >> 5);
+        bf16x8 fa[FN], fb[FM];
+#pragma unroll
+        for (int f = 0; f < FN; ++f)
+          fa[f] = *reinterpret_cast<const bf16x8*>(wstage + wrow_off[f] + ((u ^ wrow_swz[f]) << 4));
+#pragma unroll
+        for (int f = 0; f < FM; ++f)
+          fb[f] = *reinterpret_cast<const bf16x8*>(smem + xoff[f] + ((u ^ xswz[f]) << 4));
+#pragma unroll
+        for (int i = 0; i < FN; ++i)
+#pragma unroll
+          for (int j = 0; j < FM; ++j) acc[i][j] = mfma32(fa[i], fb[j], acc[i][j]);
+      }
+      slot = slot == WS - 1 ? 0 : slot + 1;
+    });
+  };
+  for (int c = 0; c < cpc - 1; ++c) chunk_body(c, std::false_type{});
+  chunk_body(cpc - 1, std::true_type{});
+
+  // add the two k-halves: waves 2, 3 park their sums in LDS, waves 0, 1 pick them up
+  wait_vmcnt<0>();
+  __syncthreads();
+  {
+    f32x4* park = reinterpret_cast<f32x4*>(smem) + (size_t)wave_m * (FN * FM * 4 * 64);
+    if (wk == 1) {
+#pragma unroll
+      for (int i = 0; i < FN; ++i)
+#pragma unroll
+        for (int j = 0; j < FM; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+            park[((i * FM + j) * 4 + g) * 64 + lane] =
+                f32x4{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+    }
+    __syncthreads();
+    if (wk == 0) {
+#pragma unroll
+      for (int i = 0; i < FN; ++i)
+#pragma unroll
+        for (int j = 0; j < FM; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const f32x4 p = park[((i * FM + j) * 4 + g) * 64 + lane];
+            acc[i][j][4 * g] += p[0]; acc[i][j][4 * g + 1] += p[1]; acc[i][j][4 * g + 2] += p[2]; acc[i][j][4 * g + 3] += p[3];
+          }
+    }
+  }
+  store_tile32<FM, FN, BN>(a, acc, m0 + wave_m * 64, c0, 0, lane, wk == 0);
+}
+
+// the patch form needs: nine taps within +-1, unit strides, coinciding input and output grids
+static bool conv_patch_applies(const GatherConvArgs& a) {
+  if (a.ntaps != 9 || a.in_stride != 1 || a.out_stride != 1 || a.ooh != 0 || a.oow != 0) return false;
+  if (a.OH != a.Hi || a.OW != a.Wi || a.OHf != a.OH || a.OWf != a.OW || a.Wi > 32 || a.Wi < 1) return false;
+  for (int i = 0; i < 9; ++i) {
+    const int dh = (a.tap[i] & 0xff) - 8, dw = ((a.tap[i] >> 8) & 0xff) - 8;
+    if (dh < -1 || dh > 1 || dw < -1 || dw > 1) return false;
+  }
+  return true;
+}
+
+template <int BN, int PR>
+static hipError_t run_patch(const GatherConvArgs& a, hipStream_t s) {
+  constexpr int WS = 5;
+  constexpr size_t lds = (size_t)2 * PR * 128 + (size_t)WS * BN * 128 + 256;
+  static_assert(lds + 2 * BN * 4 <= 160 * 1024, "LDS of one compute unit");
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_patch_kernel<BN, PR, WS>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int Mtot = a.N * a.OH * a.OW;
+  const int m_tiles = (Mtot + 127) / 128, n_tiles = (a.Co + BN - 1) / BN;
+  hipLaunchKernelGGL((conv_patch_kernel<BN, PR, WS>), dim3(m_tiles * n_tiles), dim3(256), lds, s, a, m_tiles, n_tiles);
+  return hipGetLastError();
+}
+
+template <int BN>
+static hipError_t run_patch_rows(const GatherConvArgs& a, hipStream_t s) {
+  const int rows = 128 + 2 * a.Wi + 2;   // patch rows in use
+  if (rows <= 160) return run_patch<BN, 160>(a, s);
+  if (rows <= 192) return run_patch<BN, 192>(a, s);
+  return run_patch<BN, 224>(a, s);
 }
 
 bool conv_gather_wide_applies(const GatherConvArgs& a) {
   return a.Ci % 64 == 0 && a.Co >= 128 && a.ntaps >= 1 && a.Kw % 8 == 0 && a.Hi < 32768 && a.Wi < 32768;
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES>
+template <int BN, int STAGES>
 static hipError_t run_wide(const GatherConvArgs& a, hipStream_t s) {
-  constexpr size_t lds = (size_t)STAGES * (BM + BN) * 128;
+  constexpr size_t lds = (size_t)STAGES * (128 + BN) * 128;
   static bool configured = false;   // one attribute call per instantiation (idempotent, so a race is harmless)
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_gather_dma_kernel<BM, BN, WM, WN, STAGES>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_gather_dma_kernel<BN, STAGES>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     configured = true;
   }
   const int Mtot = a.N * a.OH * a.OW;
-  const int m_tiles = (Mtot + BM - 1) / BM, n_tiles = (a.Co + BN - 1) / BN;
-  hipLaunchKernelGGL((conv_gather_dma_kernel<BM, BN, WM, WN, STAGES>), dim3(m_tiles * n_tiles), dim3(256), lds, s, a,
-                     m_tiles, n_tiles);
+  const int m_tiles = (Mtot + 127) / 128, n_tiles = (a.Co + BN - 1) / BN;
+  hipLaunchKernelGGL((conv_gather_dma_kernel<BN, STAGES>), dim3(m_tiles * n_tiles), dim3(256), lds, s, a, m_tiles, n_tiles);
   return hipGetLastError();
 }
 
 hipError_t launch_conv_gather_wide(const GatherConvArgs& a, hipStream_t s) {
   if (!conv_gather_wide_applies(a) || a.N * a.OH * a.OW <= 0) return hipErrorInvalidValue;
-  if (a.Co % 160 == 0) return run_wide<128, 160, 2, 2, 4>(a, s);
-  return run_wide<128, 128, 2, 2, 4>(a, s);
+  static const bool no_patch = getenv("FDG_NO_PATCH") != nullptr;
+  if (conv_patch_applies(a) && !no_patch) return a.Co % 160 == 0 ? run_patch_rows<160>(a, s) : run_patch_rows<128>(a, s);
+  if (a.Co % 160 == 0) return run_wide<160, 4>(a, s);
+  return run_wide<128, 4>(a, s);
 }
-
 
 // ------------------------------------------------------------------------------------------------
 // Weight gradient for wide layers: dw[co, tap, ci] += sum_pixel dy[pixel, co] * x[pixel + tap, ci]
