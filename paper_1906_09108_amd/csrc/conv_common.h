@@ -108,80 +108,136 @@ __device__ __forceinline__ void store_tile(const GatherConvArgs& a, const f32x4 
   }
 }
 
-// The same output stage for 32x32 accumulator blocks: acc[i][j] covers channels c_base + 32 i .. and pixels
-// m_base + 32 j ..; lane l holds pixel (l & 31) and, in components 4g..4g+3, channels 8g + 4*(l >> 5) .. +3.
-template <int FM, int FN, int BN>
-__device__ __forceinline__ void store_tile32(const GatherConvArgs& a, const f32x16 (&acc)[FN][FM], int m_base, int c_tile,
-                                             int c_wave, int lane, bool active) {
+// Output stage for 32x32 accumulator blocks, one wave = 32 pixels x BN channels.
+// acc[i] covers channels c_tile + 32 i .. +31: lane l holds pixel m_base + (l & 31) and, in components
+// 4g..4g+3, channels 8g + 4*(l >> 5) .. +3 of the block.  A lane per pixel would write 8- or 16-byte pieces
+// 2*Co bytes apart, so the block is first turned through LDS (rows of BN floats, padded by 16 bytes so that
+// the 16-byte column writes of 16 consecutive pixels fall into different banks) and then leaves row by row:
+// consecutive lanes carry consecutive 4-channel units of a pixel, which makes the addend and mask reads and
+// the fp32 / bf16 stores contiguous runs of BN channels.  `lds` is this wave's private region of
+// OUT_STAGE_BYTES(BN) bytes; the main loop's LDS traffic of the whole workgroup must be over.
+// Must be called by all threads of the workgroup (the statistics are combined through LDS).
+constexpr int out_stage_pitch(int BN) { return BN * 4 + 16; }
+constexpr int out_stage_bytes(int BN) { return 32 * out_stage_pitch(BN) + 128; }
+
+template <int FN, int BN>
+__device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x16 (&acc)[FN], int m_base, int c_tile,
+                                             int lane, unsigned char* lds) {
+  static_assert(FN * 32 == BN, "one wave carries all channels of the tile");
+  constexpr int PITCH = out_stage_pitch(BN);
+  constexpr int UNITS = BN / 4;                       // 16-byte fp32 units per pixel
+  constexpr int ITERS = 32 * UNITS / 64;
+  constexpr int PERIOD = UNITS % 64 == 0 ? 1 : (UNITS % 32 == 0 ? 1 : (UNITS % 16 == 0 ? UNITS / 16 : (UNITS % 8 == 0 ? UNITS / 8 : UNITS)));
+  static_assert((64 * PERIOD) % UNITS == 0 && ITERS % PERIOD == 0, "unit assignment repeats every PERIOD iterations");
   const int Mtot = a.N * a.OH * a.OW;
-  const int c_base = c_tile + c_wave;
-  float s1[FN][16], s2[FN][16];
-#pragma unroll
-  for (int i = 0; i < FN; ++i)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) s1[i][v] = s2[i][v] = 0.f;
-#pragma unroll
-  for (int j = 0; j < FM; ++j) {
-    const int m = m_base + j * 32 + (lane & 31);
-    if (m >= Mtot || !active) continue;
-    const int ow = m % a.OW, t2 = m / a.OW, oh = t2 % a.OH, n = t2 / a.OH;
-    const size_t opix = ((size_t)n * a.OHf + oh * a.out_stride + a.ooh) * a.OWf + ow * a.out_stride + a.oow;
+  {
+    const int p = lane & 31, half = lane >> 5;
 #pragma unroll
     for (int i = 0; i < FN; ++i)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int c = c_base + i * 32 + 8 * g + 4 * (lane >> 5);
-        if (c >= a.Co) continue;
-        const size_t o = opix * a.Co + c;
-        float v0 = acc[i][j][4 * g], v1 = acc[i][j][4 * g + 1], v2 = acc[i][j][4 * g + 2], v3 = acc[i][j][4 * g + 3];
-        if (a.addend) {
-          float4 ad = *reinterpret_cast<const float4*>(a.addend + o);
-          if (a.addmask) {
-            const uint2 mk = *reinterpret_cast<const uint2*>(a.addmask + o);
-            if (!(bf16_lo(mk.x) > 0.f)) ad.x = 0.f;
-            if (!(bf16_hi(mk.x) > 0.f)) ad.y = 0.f;
-            if (!(bf16_lo(mk.y) > 0.f)) ad.z = 0.f;
-            if (!(bf16_hi(mk.y) > 0.f)) ad.w = 0.f;
-          }
-          v0 += ad.x; v1 += ad.y; v2 += ad.z; v3 += ad.w;
-        }
-        if (a.out_f32) *reinterpret_cast<float4*>(a.out_f32 + o) = make_float4(v0, v1, v2, v3);
-        const uint2 packed = make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
-        if (a.out_b16) *reinterpret_cast<uint2*>(a.out_b16 + o) = packed;
-        if (a.stats) {
-          const float r0 = bf16_lo(packed.x), r1 = bf16_hi(packed.x), r2 = bf16_lo(packed.y), r3 = bf16_hi(packed.y);
-          s1[i][4 * g] += r0; s1[i][4 * g + 1] += r1; s1[i][4 * g + 2] += r2; s1[i][4 * g + 3] += r3;
-          s2[i][4 * g] += r0 * r0; s2[i][4 * g + 1] += r1 * r1; s2[i][4 * g + 2] += r2 * r2; s2[i][4 * g + 3] += r3 * r3;
-        }
+      for (int g = 0; g < 4; ++g)
+        *reinterpret_cast<f32x4*>(lds + p * PITCH + (i * 32 + 8 * g + 4 * half) * 4) =
+            f32x4{acc[i][4 * g], acc[i][4 * g + 1], acc[i][4 * g + 2], acc[i][4 * g + 3]};
+    if (lane < 32) {
+      const int m = m_base + lane;
+      int pix = -1;
+      if (m < Mtot) {
+        const int ow = m % a.OW, t2 = m / a.OW, oh = t2 % a.OH, n = t2 / a.OH;
+        pix = (n * a.OHf + oh * a.out_stride + a.ooh) * a.OWf + ow * a.out_stride + a.oow;
       }
+      *reinterpret_cast<int*>(lds + 32 * PITCH + 4 * lane) = pix;
+    }
+  }
+  asm volatile("" ::: "memory");   // same wave, LDS operations stay in order: no barrier needed
+  float s1[PERIOD][4], s2[PERIOD][4];
+#pragma unroll
+  for (int k = 0; k < PERIOD; ++k)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) s1[k][e] = s2[k][e] = 0.f;
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    const int q = it * 64 + lane;
+    const int p = q / UNITS, un = q % UNITS;
+    const int pix = *reinterpret_cast<const int*>(lds + 32 * PITCH + 4 * p);
+    const int c = c_tile + un * 4;
+    if (pix < 0 || c >= a.Co) continue;
+    f32x4 v = *reinterpret_cast<const f32x4*>(lds + p * PITCH + un * 16);
+    const size_t o = (size_t)pix * a.Co + c;
+    if (a.addend) {
+      float4 ad = *reinterpret_cast<const float4*>(a.addend + o);
+      if (a.addmask) {
+        const uint2 mk = *reinterpret_cast<const uint2*>(a.addmask + o);
+        if (!(bf16_lo(mk.x) > 0.f)) ad.x = 0.f;
+        if (!(bf16_hi(mk.x) > 0.f)) ad.y = 0.f;
+        if (!(bf16_lo(mk.y) > 0.f)) ad.z = 0.f;
+        if (!(bf16_hi(mk.y) > 0.f)) ad.w = 0.f;
+      }
+      v[0] += ad.x; v[1] += ad.y; v[2] += ad.z; v[3] += ad.w;
+    }
+    if (a.out_f32) *reinterpret_cast<float4*>(a.out_f32 + o) = make_float4(v[0], v[1], v[2], v[3]);
+    const uint2 packed = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+    if (a.out_b16) *reinterpret_cast<uint2*>(a.out_b16 + o) = packed;
+    if (a.stats) {
+      const float r0 = bf16_lo(packed.x), r1 = bf16_hi(packed.x), r2 = bf16_lo(packed.y), r3 = bf16_hi(packed.y);
+      const int k = it % PERIOD;
+      s1[k][0] += r0; s1[k][1] += r1; s1[k][2] += r2; s1[k][3] += r3;
+      s2[k][0] += r0 * r0; s2[k][1] += r1 * r1; s2[k][2] += r2 * r2; s2[k][3] += r3 * r3;
+    }
   }
   if (a.stats) {
+    // per-channel sums of the workgroup in LDS (LDS atomics: at most two lanes of an instruction share a
+    // channel), then one global atomic per channel and value
     __shared__ float red[2 * BN];
-    __syncthreads();
+    __syncthreads();   // every wave has finished with the shared regions the caller may have overlapped
     for (int t = threadIdx.x; t < 2 * BN; t += blockDim.x) red[t] = 0.f;
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < FN; ++i)
+    for (int k = 0; k < PERIOD; ++k) {
+      const int un = (k * 64 + lane) % UNITS;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        float x1 = s1[i][v], x2 = s2[i][v];
-#pragma unroll
-        for (int off = 16; off > 0; off >>= 1) {   // the 32 lanes with equal (lane >> 5) hold the same channels
-          x1 += __shfl_xor(x1, off, 32);
-          x2 += __shfl_xor(x2, off, 32);
-        }
-        if ((lane & 31) == 0 && active) {
-          const int cl = c_wave + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-          atomicAdd(&red[cl], x1);
-          atomicAdd(&red[BN + cl], x2);
-        }
+      for (int e = 0; e < 4; ++e) {
+        atomicAdd(&red[un * 4 + e], s1[k][e]);
+        atomicAdd(&red[BN + un * 4 + e], s2[k][e]);
       }
+    }
     __syncthreads();
     for (int t = threadIdx.x; t < 2 * BN; t += blockDim.x) {
       const int c = c_tile + (t % BN);
       if (c < a.Co) atomicAdd(a.stats + (t / BN) * a.Co + c, red[t]);
     }
   }
+}
+
+// End of a wide kernel whose four waves are (wave_m, wk): wave_m owns 64 pixels as two 32-pixel blocks j, wk
+// one half of the contraction.  The two halves are added through LDS so that every wave ends with one
+// 32-pixel block (wave wk keeps block j = wk and receives its partner's), then all four run the output stage.
+// smem must hold max(4 * FN * 16 * 256, 4 * out_stage_bytes(BN)) bytes and be idle (no loads in flight).
+template <int FN, int BN>
+__device__ __forceinline__ void combine_and_store32(const GatherConvArgs& a, f32x16 (&acc)[FN][2], int m_tile, int c_tile,
+                                                    int wave_m, int wk, int lane, unsigned char* smem) {
+  __syncthreads();
+  f32x4* mine = reinterpret_cast<f32x4*>(smem) + (size_t)(wave_m * 2 + wk) * (FN * 4 * 64);
+  const f32x4* theirs = reinterpret_cast<const f32x4*>(smem) + (size_t)(wave_m * 2 + (wk ^ 1)) * (FN * 4 * 64);
+  f32x16 keep[FN];
+#pragma unroll
+  for (int i = 0; i < FN; ++i) {
+    const f32x16 give = wk == 0 ? acc[i][1] : acc[i][0];
+    keep[i] = wk == 0 ? acc[i][0] : acc[i][1];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      mine[(i * 4 + g) * 64 + lane] = f32x4{give[4 * g], give[4 * g + 1], give[4 * g + 2], give[4 * g + 3]};
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < FN; ++i)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const f32x4 p = theirs[(i * 4 + g) * 64 + lane];
+      keep[i][4 * g] += p[0]; keep[i][4 * g + 1] += p[1]; keep[i][4 * g + 2] += p[2]; keep[i][4 * g + 3] += p[3];
+    }
+  __syncthreads();
+  const int wave = wave_m * 2 + wk;
+  store_rows32<FN, BN>(a, keep, m_tile + wave_m * 64 + wk * 32, c_tile, lane, smem + (size_t)wave * out_stage_bytes(BN));
 }
 
 // The wide-channel kernel (conv_wide_kernels.hip): input channels a multiple of 64.

@@ -46,7 +46,7 @@ __global__ __launch_bounds__(256) void conv_gather_dma_kernel(GatherConvArgs a, 
   constexpr int NJ = JX + JW;
   constexpr int FM = 2, FN = BN / 32;
   static_assert((STAGES - 2) * NJ < 64, "vmcnt range");
-  static_assert((size_t)STAGES * R * ROWB >= (size_t)2 * FN * FM * 16 * 64 * 4, "room to park the partial sums");
+  static_assert((size_t)STAGES * R * ROWB >= (size_t)4 * FN * 16 * 256 && (size_t)STAGES * R * ROWB >= (size_t)4 * out_stage_bytes(BN), "room for the output stage");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // STAGES * R * ROWB
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -154,35 +154,8 @@ __global__ __launch_bounds__(256) void conv_gather_dma_kernel(GatherConvArgs a, 
         for (int j = 0; j < FM; ++j) acc[i][j] = mfma32(fa[i], fb[j], acc[i][j]);
     }
   }
-  // add the two k-halves: waves 2, 3 park their sums in LDS, waves 0, 1 pick them up
   wait_vmcnt<0>();
-  __syncthreads();
-  {
-    f32x4* park = reinterpret_cast<f32x4*>(smem) + (size_t)wave_m * (FN * FM * 4 * 64);
-    if (wk == 1) {
-#pragma unroll
-      for (int i = 0; i < FN; ++i)
-#pragma unroll
-        for (int j = 0; j < FM; ++j)
-#pragma unroll
-          for (int g = 0; g < 4; ++g)
-            park[((i * FM + j) * 4 + g) * 64 + lane] =
-                f32x4{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-    }
-    __syncthreads();
-    if (wk == 0) {
-#pragma unroll
-      for (int i = 0; i < FN; ++i)
-#pragma unroll
-        for (int j = 0; j < FM; ++j)
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const f32x4 p = park[((i * FM + j) * 4 + g) * 64 + lane];
-            acc[i][j][4 * g] += p[0]; acc[i][j][4 * g + 1] += p[1]; acc[i][j][4 * g + 2] += p[2]; acc[i][j][4 * g + 3] += p[3];
-          }
-    }
-  }
-  store_tile32<FM, FN, BN>(a, acc, m0 + wave_m * 64, c0, 0, lane, wk == 0);
+  combine_and_store32<FN, BN>(a, acc, m0, c0, wave_m, wk, lane, smem);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -218,7 +191,7 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
   constexpr int ZOFF = 2 * XBYTES + WS * WBYTES;   // 256 bytes of zeros
   static_assert((WS - 2) * JW + JX < 64, "vmcnt range");
   static_assert(WS >= 3 && WS <= 9, "pipeline depth");
-  static_assert((size_t)ZOFF >= (size_t)2 * FN * FM * 16 * 64 * 4, "room to park the partial sums");
+  static_assert((size_t)ZOFF >= (size_t)4 * FN * 16 * 256 && (size_t)ZOFF >= (size_t)4 * out_stage_bytes(BN), "room for the output stage");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // ZOFF + 256
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -262,18 +235,12 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
   }
   const int cpc = a.Ci >> 6;   // channel blocks
 
-  auto issue_x = [&](int c) {
-    unsigned char* stage = smem + (c & 1) * XBYTES;
-    const int cb = c * 128;
-#pragma unroll
-    for (int j = 0; j < JX; ++j) dma16(xsrc[j] ? xsrc[j] + cb : zero, stage + (8 * (4 * j + wave)) * ROWB);
+  auto issue_x_one = [&](int j, int c) {
+    dma16(xsrc[j] ? xsrc[j] + c * 128 : zero, smem + (c & 1) * XBYTES + (8 * (4 * j + wave)) * ROWB);
   };
-  auto issue_w = [&](int slot, int kbyte) {
-    unsigned char* stage = smem + 2 * XBYTES + slot * WBYTES;
-#pragma unroll
-    for (int j = 0; j < JW; ++j) dma16(wsrc[j] ? wsrc[j] + kbyte : zero, stage + (8 * (4 * j + wave)) * ROWB);
+  auto issue_w_one = [&](int j, int slot, int kbyte) {
+    dma16(wsrc[j] ? wsrc[j] + kbyte : zero, smem + 2 * XBYTES + slot * WBYTES + (8 * (4 * j + wave)) * ROWB);
   };
-
   f32x16 acc[FN][FM];
 #pragma unroll
   for (int i = 0; i < FN; ++i)
@@ -304,90 +271,104 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
     wrow_swz[f] = (row >> 1) & 7;
   }
 
-  issue_x(0);
 #pragma unroll
-  for (int p = 0; p < WS - 1; ++p) issue_w(p, tko[p]);   // 9 taps >= WS - 1 steps always exist
+  for (int j = 0; j < JX; ++j) issue_x_one(j, 0);
+#pragma unroll
+  for (int p = 0; p < WS - 1; ++p)   // 9 taps >= WS - 1 steps always exist
+#pragma unroll
+    for (int j = 0; j < JW; ++j) issue_w_one(j, p, tko[p]);
+
+  // Operand fragments, two sets: while the MFMAs of one 16-channel half step run from one set, the reads of
+  // the next half step fill the other, so LDS latency stays behind the matrix pipe even with one wave per
+  // SIMD.  The compiler's scheduler would undo this to save registers, so each half step is written as
+  // NM (MFMA, piece of other work) pairs pinned with scheduling barriers.
+  constexpr int NM = FN * FM, NFRAG = FN + FM;
+  static_assert(NFRAG + 2 <= NM && 2 + JW < NM, "slots of a half step");
+  bf16x8 fa[2][FN], fb[2][FM];
+  // fragment idx of a half step in the order the MFMAs need them: B0, A0, B1, A1, A2, ...
+  auto read_one = [&](auto set_tag, auto idx_tag, int wslot, int xbuf, auto tap_tag, int ss) {
+    constexpr int S = decltype(set_tag)::value, IDX = decltype(idx_tag)::value, T = decltype(tap_tag)::value;
+    const int u = 4 * wk + 2 * ss + (lane >> 5);
+    if constexpr (IDX == 0 || IDX == 2) {
+      constexpr int f = IDX / 2;
+      // patch row of this tap, or the zero region (same bank position, so it never adds a conflict)
+      const int p = prow[f] + tdh[T] * W + tdw[T];
+      const bool ok = (unsigned)(poh[f] + tdh[T]) < (unsigned)H && (unsigned)(pow_[f] + tdw[T]) < (unsigned)W;
+      const int off = ok ? xbuf * XBYTES + p * ROWB : ZOFF + (p & 1) * ROWB;
+      fb[S][f] = *reinterpret_cast<const bf16x8*>(smem + off + ((u ^ ((p >> 1) & 7)) << 4));
+    } else {
+      constexpr int f = IDX == 1 ? 0 : IDX - 2;
+      fa[S][f] = *reinterpret_cast<const bf16x8*>(smem + 2 * XBYTES + wslot * WBYTES + wrow_off[f] + ((u ^ wrow_swz[f]) << 4));
+    }
+  };
+  auto mma_one = [&](auto set_tag, auto k_tag) {
+    constexpr int S = decltype(set_tag)::value, K = decltype(k_tag)::value;
+    acc[K / FM][K % FM] = mfma32(fa[S][K / FM], fb[S][K % FM], acc[K / FM][K % FM]);
+  };
+  using set0 = std::integral_constant<int, 0>;
+  using set1 = std::integral_constant<int, 1>;
+
+  // Barrier e makes step e visible and is taken inside step e - 1.  Before it every wave has finished
+  // reading step e - 2, whose weight stage therefore receives step e + WS - 2 right after it.
+  wait_vmcnt<(WS - 2) * JW>();
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  static_for<NFRAG>([&](auto idx) { read_one(set0{}, idx, 0, 0, std::integral_constant<int, 0>{}, 0); });
 
   int slot = 0;   // weight stage of the current step
   auto chunk_body = [&](int c, auto last_tag) {
     constexpr bool LAST = decltype(last_tag)::value;
-    const unsigned char* xstage = smem + (c & 1) * XBYTES;
     static_for<9>([&](auto t_tag) {
       constexpr int T = decltype(t_tag)::value;
-      constexpr int AHEAD = LAST ? ((8 - T) < (WS - 2) ? (8 - T) : (WS - 2)) : (WS - 2);
-      constexpr int XPEND = (!LAST && T >= 1 && T <= WS - 1) ? JX : 0;
-      wait_vmcnt<AHEAD * JW + XPEND>();
-      asm volatile("" ::: "memory");
-      __builtin_amdgcn_s_barrier();
-      asm volatile("" ::: "memory");
-      constexpr int TT = T + WS - 1;                // tap of the step issued now
-      if constexpr (TT < 9) {
-        issue_w(slot == 0 ? WS - 1 : slot - 1, tko[TT] + c * 128);
-      } else if constexpr (!LAST) {
-        issue_w(slot == 0 ? WS - 1 : slot - 1, tko[TT - 9] + (c + 1) * 128);
-      }
-      if constexpr (T == 0 && !LAST) issue_x(c + 1);
-
-      const unsigned char* wstage = smem + 2 * XBYTES + slot * WBYTES;
-      // patch rows of this tap, or the zero region (same bank position, so it never adds a conflict)
-      int xoff[FM], xswz[FM];
+      // first half step: MFMAs of set 0, reads of this step's second half into set 1
+      static_for<NM>([&](auto k) {
+        constexpr int K = decltype(k)::value;
+        mma_one(set0{}, k);
+        if constexpr (K < NFRAG) read_one(set1{}, k, slot, c & 1, t_tag, 1);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      // second half step: MFMAs of set 1; barrier, then the next step's first reads and the DMA issue
+      const int nslot = slot == WS - 1 ? 0 : slot + 1;
+      const int islot = slot == 0 ? WS - 1 : slot - 1;
+      constexpr bool MORE = !(LAST && T == 8);            // a next step exists
+      constexpr int TT = T + WS - 1;                      // tap of the step issued now
+      constexpr bool ISSUE_W = TT < 9 || !LAST;
+      constexpr bool ISSUE_X = T == 0 && !LAST;
+      const int kbyte = TT < 9 ? tko[TT < 9 ? TT : 0] + c * 128 : tko[TT < 9 ? 0 : TT - 9] + (c + 1) * 128;
+      static_for<NM>([&](auto k) {
+        constexpr int K = decltype(k)::value;
+        mma_one(set1{}, k);
+        if constexpr (MORE) {
+          if constexpr (K == 1) {
+            constexpr int AHEAD = LAST ? ((7 - T) < (WS - 3) ? (7 - T) : (WS - 3)) : (WS - 3);
+            constexpr int XPEND = (!LAST && T >= 1 && T <= WS - 2) ? JX : 0;
+            wait_vmcnt<AHEAD * JW + XPEND>();
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+          }
+          if constexpr (K >= 2 && K - 2 < NFRAG) {
+            if constexpr (T < 8) read_one(set0{}, std::integral_constant<int, K - 2>{}, nslot, c & 1, std::integral_constant<int, (T + 1) % 9>{}, 0);
+            else read_one(set0{}, std::integral_constant<int, K - 2>{}, nslot, (c + 1) & 1, std::integral_constant<int, 0>{}, 0);
+          }
+          if constexpr (ISSUE_W && K >= 2 && K - 2 < JW) issue_w_one(K - 2, islot, kbyte);
+          if constexpr (ISSUE_X && K >= 2 + JW) {
+            constexpr int XSLOTS = NM - 2 - JW, PER = (JX + XSLOTS - 1) / XSLOTS;
 #pragma unroll
-      for (int f = 0; f < FM; ++f) {
-        const int p = prow[f] + tdh[T] * W + tdw[T];
-        const bool ok = (unsigned)(poh[f] + tdh[T]) < (unsigned)H && (unsigned)(pow_[f] + tdw[T]) < (unsigned)W;
-        xswz[f] = (p >> 1) & 7;
-        xoff[f] = ok ? (int)(xstage - smem) + p * ROWB : ZOFF + (p & 1) * ROWB;
-      }
-#pragma unroll
-      for (int ss = 0; ss < 2; ++ss) {
-        const int u = 4 * wk + 2 * ss + (lane >> 5);
-        bf16x8 fa[FN], fb[FM];
-#pragma unroll
-        for (int f = 0; f < FN; ++f)
-          fa[f] = *reinterpret_cast<const bf16x8*>(wstage + wrow_off[f] + ((u ^ wrow_swz[f]) << 4));
-#pragma unroll
-        for (int f = 0; f < FM; ++f)
-          fb[f] = *reinterpret_cast<const bf16x8*>(smem + xoff[f] + ((u ^ xswz[f]) << 4));
-#pragma unroll
-        for (int i = 0; i < FN; ++i)
-#pragma unroll
-          for (int j = 0; j < FM; ++j) acc[i][j] = mfma32(fa[i], fb[j], acc[i][j]);
-      }
-      slot = slot == WS - 1 ? 0 : slot + 1;
+            for (int j = (K - 2 - JW) * PER; j < (K - 1 - JW) * PER && j < JX; ++j) issue_x_one(j, c + 1);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      slot = nslot;
     });
   };
   for (int c = 0; c < cpc - 1; ++c) chunk_body(c, std::false_type{});
   chunk_body(cpc - 1, std::true_type{});
 
-  // add the two k-halves: waves 2, 3 park their sums in LDS, waves 0, 1 pick them up
   wait_vmcnt<0>();
-  __syncthreads();
-  {
-    f32x4* park = reinterpret_cast<f32x4*>(smem) + (size_t)wave_m * (FN * FM * 4 * 64);
-    if (wk == 1) {
-#pragma unroll
-      for (int i = 0; i < FN; ++i)
-#pragma unroll
-        for (int j = 0; j < FM; ++j)
-#pragma unroll
-          for (int g = 0; g < 4; ++g)
-            park[((i * FM + j) * 4 + g) * 64 + lane] =
-                f32x4{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-    }
-    __syncthreads();
-    if (wk == 0) {
-#pragma unroll
-      for (int i = 0; i < FN; ++i)
-#pragma unroll
-        for (int j = 0; j < FM; ++j)
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const f32x4 p = park[((i * FM + j) * 4 + g) * 64 + lane];
-            acc[i][j][4 * g] += p[0]; acc[i][j][4 * g + 1] += p[1]; acc[i][j][4 * g + 2] += p[2]; acc[i][j][4 * g + 3] += p[3];
-          }
-    }
-  }
-  store_tile32<FM, FN, BN>(a, acc, m0 + wave_m * 64, c0, 0, lane, wk == 0);
+  combine_and_store32<FN, BN>(a, acc, m0, c0, wave_m, wk, lane, smem);
 }
 
 // the patch form needs: nine taps within +-1, unit strides, coinciding input and output grids
