@@ -130,6 +130,16 @@ __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x
   constexpr int PERIOD = UNITS % 64 == 0 ? 1 : (UNITS % 32 == 0 ? 1 : (UNITS % 16 == 0 ? UNITS / 16 : (UNITS % 8 == 0 ? UNITS / 8 : UNITS)));
   static_assert((64 * PERIOD) % UNITS == 0 && ITERS % PERIOD == 0, "unit assignment repeats every PERIOD iterations");
   const int Mtot = a.N * a.OH * a.OW;
+  // The arguments live in constant memory, and a compiler short of scalar registers re-reads them at every
+  // use: one scalar load and a full wait per pointer test, twenty times over.  Read what the row loop needs
+  // once, into values the compiler cannot trace back to memory.
+  const float* addend = a.addend;
+  const bf16_t* addmask = a.addmask;
+  float* out_f32 = a.out_f32;
+  bf16_t* out_b16 = a.out_b16;
+  int Co = a.Co;
+  int want_stats = a.stats != nullptr;
+  asm volatile("" : "+v"(addend), "+v"(addmask), "+v"(out_f32), "+v"(out_b16), "+v"(Co), "+v"(want_stats));
   {
     const int p = lane & 31, half = lane >> 5;
 #pragma unroll
@@ -160,13 +170,13 @@ __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x
     const int p = q / UNITS, un = q % UNITS;
     const int pix = *reinterpret_cast<const int*>(lds + 32 * PITCH + 4 * p);
     const int c = c_tile + un * 4;
-    if (pix < 0 || c >= a.Co) continue;
+    if (pix < 0 || c >= Co) continue;
     f32x4 v = *reinterpret_cast<const f32x4*>(lds + p * PITCH + un * 16);
-    const size_t o = (size_t)pix * a.Co + c;
-    if (a.addend) {
-      float4 ad = *reinterpret_cast<const float4*>(a.addend + o);
-      if (a.addmask) {
-        const uint2 mk = *reinterpret_cast<const uint2*>(a.addmask + o);
+    const size_t o = (size_t)pix * Co + c;
+    if (addend) {
+      float4 ad = *reinterpret_cast<const float4*>(addend + o);
+      if (addmask) {
+        const uint2 mk = *reinterpret_cast<const uint2*>(addmask + o);
         if (!(bf16_lo(mk.x) > 0.f)) ad.x = 0.f;
         if (!(bf16_hi(mk.x) > 0.f)) ad.y = 0.f;
         if (!(bf16_lo(mk.y) > 0.f)) ad.z = 0.f;
@@ -174,10 +184,10 @@ __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x
       }
       v[0] += ad.x; v[1] += ad.y; v[2] += ad.z; v[3] += ad.w;
     }
-    if (a.out_f32) *reinterpret_cast<float4*>(a.out_f32 + o) = make_float4(v[0], v[1], v[2], v[3]);
+    if (out_f32) *reinterpret_cast<float4*>(out_f32 + o) = make_float4(v[0], v[1], v[2], v[3]);
     const uint2 packed = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
-    if (a.out_b16) *reinterpret_cast<uint2*>(a.out_b16 + o) = packed;
-    if (a.stats) {
+    if (out_b16) *reinterpret_cast<uint2*>(out_b16 + o) = packed;
+    if (want_stats) {
       const float r0 = bf16_lo(packed.x), r1 = bf16_hi(packed.x), r2 = bf16_lo(packed.y), r3 = bf16_hi(packed.y);
       const int k = it % PERIOD;
       s1[k][0] += r0; s1[k][1] += r1; s1[k][2] += r2; s1[k][3] += r3;
