@@ -256,5 +256,8 @@ hipError_t launch_conv_gather_wide(const GatherConvArgs& a, hipStream_t s);
 // The wide-channel weight gradient: output and input channels multiples of 160, output width dividing 64.
 bool conv_wgrad_wide_applies(const WgradArgs& a);
 hipError_t launch_conv_wgrad_wide(const WgradArgs& a, hipStream_t s);
+// The same for channel counts that are multiples of 128: 128 x 128 blocks, contraction split over the waves.
+bool conv_wgrad128_applies(const WgradArgs& a);
+hipError_t launch_conv_wgrad128(const WgradArgs& a, hipStream_t s);
 
 }  // namespace fdg

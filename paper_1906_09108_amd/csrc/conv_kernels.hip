@@ -13,6 +13,7 @@
 // column (l & 15) of B, each with the 8 consecutive k values 8*(l >> 4) .. +7; lane l receives
 // D[4*(l >> 4) + v][l & 15] in accumulator component v.
 #include "conv_common.h"
+#include <stdlib.h>
 
 namespace fdg {
 
@@ -327,6 +328,8 @@ static hipError_t run_wgrad(const WgradArgs& a, hipStream_t s) {
 hipError_t launch_conv_wgrad(const WgradArgs& a, hipStream_t s) {
   if (a.Co % 8 != 0 || a.Cx % 8 != 0 || a.Ci > a.Cx || a.ntaps < 1 || a.ntaps > 9 || a.N * a.OH * a.OW <= 0)
     return hipErrorInvalidValue;
+  static const bool old_wide = getenv("FDG_WGRAD_160") != nullptr;   // A/B switch for measurements
+  if (conv_wgrad128_applies(a) && !(old_wide && conv_wgrad_wide_applies(a))) return launch_conv_wgrad128(a, s);
   if (conv_wgrad_wide_applies(a)) return launch_conv_wgrad_wide(a, s);
   if (a.Co <= 64 && a.Cx <= 64) return run_wgrad<32, 32, 1, 1, 4>(a, s);
   return run_wgrad<128, 128, 2, 2, 1>(a, s);
@@ -401,7 +404,8 @@ hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, co
 size_t conv_wgrad_scratch_bytes(const ConvShape& c) {
   WgradArgs a{};
   a.Co = c.Co; a.Ci = c.Ci; a.Cx = c.Cip; a.OW = c.Wo(); a.ntaps = c.T;
-  return conv_wgrad_wide_applies(a) ? (size_t)8 * c.Co * c.T * c.Ci * 4 : 0;
+  a.N = c.N; a.OH = c.Ho(); a.Hi = c.Hi; a.Wi = c.Wi; a.stride = c.stride;
+  return (conv_wgrad_wide_applies(a) || conv_wgrad128_applies(a)) ? (size_t)8 * c.Co * c.T * c.Ci * 4 : 0;
 }
 
 hipError_t conv_wgrad(const ConvShape& c, const bf16_t* x, const bf16_t* dy, float* dw, float* scratch,

@@ -621,6 +621,324 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(float4* __restrict__ 
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Weight gradient, 128 x 128 blocks on 32x32x16 MFMAs
+// ------------------------------------------------------------------------------------------------
+// Same wave layout as the forward kernels: wave_m = wave & 1 owns 64 of the block's 128 output channels (all
+// 128 input channels: 2 x 4 accumulator blocks), wk = wave >> 1 one 32-pixel half of every 64-pixel chunk, and
+// the two halves are added through LDS at the end.  (Letting every wave own the whole block and a quarter of
+// the pixels would read each staged byte exactly once, but 256 accumulator registers leave the compiler no
+// room and it spills.)  Tiles are [pixel][128 channels] (256-byte rows) read with the transposing LDS load;
+// the 32-byte slot of a row is XORed with 2 * (pixel & 3) so that the 4 pixels x 2 channel blocks a half wave
+// reads in one pass cover all banks.  The x source of a row advances by a constant per chunk (the launcher
+// requires Hi == stride * OH and OW | 64), and whether the row falls into the padding repeats with a short
+// period over the chunks, so row validity is a per-lane bit mask indexed by chunk phase.  Operand reads run
+// one half step ahead of the MFMAs, pinned with scheduling barriers as in the patch kernel.
+struct Wgrad128Launch {
+  int co_tiles, ci_tiles, splits, chunks_per_split;
+  float* partial;        // when set: split s stores its block at partial + s * split_stride
+  size_t split_stride;
+  int period;            // row validity repeats every `period` chunks
+  int d_oh;              // output rows per chunk (64 / OW), reduced mod OH
+  long long a_step, b_step;   // bytes from one chunk to the next in dy and in x
+};
+
+template <int STAGES>
+__global__ __launch_bounds__(256) void conv_wgrad128_kernel(WgradArgs a, Wgrad128Launch L) {
+  constexpr int BC = 128, BKP = 64, ROWB = BC * 2, PART = BKP * ROWB, JP = 4, NJ = 2 * JP;
+  constexpr int FA = 2, FB = 4, NF = FA + FB, NM = FA * FB;   // fragments and MFMAs per 16-pixel step
+  static_assert(STAGES >= 3 && (STAGES - 2) * NJ < 64, "pipeline depth / vmcnt range");
+  static_assert(STAGES * 2 * PART >= 4 * 16 * 1024, "room for the exchange of the partial blocks");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // STAGES * 2 * PART
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave_m = wave & 1, wk = wave >> 1;
+
+  int t = blockIdx.x;
+  const int total = gridDim.x;
+  if ((total & 7) == 0) t = (blockIdx.x & 7) * (total >> 3) + (blockIdx.x >> 3);
+  const int ci_t = t % L.ci_tiles; t /= L.ci_tiles;
+  const int co_t = t % L.co_tiles; t /= L.co_tiles;
+  const int tapi = t % a.ntaps;
+  const int split = t / a.ntaps;
+  const int co0 = co_t * BC, ci0 = ci_t * BC;
+  const int tp = a.tap[tapi];
+  const int dh = (tp & 0xff) - 8, dw = ((tp >> 8) & 0xff) - 8;
+  const int total_chunks = (a.N * a.OH * a.OW) / BKP;
+  const int chunk_lo = split * L.chunks_per_split;
+  const int n = min(total_chunks, chunk_lo + L.chunks_per_split) - chunk_lo;
+  if (n <= 0) return;
+
+  // ---- per-thread DMA sources: instruction j of this wave covers pixel rows 4*(4j+wave) .. +3 ----
+  const char* aptr[JP];
+  const char* bptr[JP];
+  unsigned bmask[JP];
+#pragma unroll
+  for (int j = 0; j < JP; ++j) {
+    const int r = 4 * (4 * j + wave) + (lane >> 4), up = lane & 15;
+    const int u = 2 * ((up >> 1) ^ (2 * (r & 3))) + (up & 1);
+    const int m = chunk_lo * BKP + r;
+    aptr[j] = reinterpret_cast<const char*>(a.dy) + ((size_t)m * a.Co + co0 + u * 8) * 2;
+    const int ow = m % a.OW, t2 = m / a.OW, oh = t2 % a.OH, nimg = t2 / a.OH;
+    const int iw = ow * a.stride + dw;
+    const bool colok = (unsigned)iw < (unsigned)a.Wi;
+    bptr[j] = reinterpret_cast<const char*>(a.x) +
+              ((((long long)nimg * a.Hi + oh * a.stride + dh) * a.Wi + iw) * a.Cx + ci0 + u * 8) * 2;
+    unsigned mask = 0;
+    int ohq = oh;
+    for (int q = 0; q < L.period; ++q) {
+      if (colok && (unsigned)(ohq * a.stride + dh) < (unsigned)a.Hi) mask |= 1u << q;
+      ohq += L.d_oh;
+      if (ohq >= a.OH) ohq -= a.OH;
+    }
+    bmask[j] = mask;
+  }
+  const char* zero = reinterpret_cast<const char*>(g_zero_word);
+
+  int issue_phase = 0;   // (chunk being issued) mod period
+  auto issue_one = [&](int d, int c) {   // piece d of chunk c (relative to chunk_lo)
+    unsigned char* stage = smem + (size_t)(c % STAGES) * (2 * PART);
+    if (d < JP) {
+      dma16(aptr[d] + (long long)c * L.a_step, stage + (64 * (4 * d + wave)) * 16);
+    } else {
+      const int j = d - JP;
+      const bool ok = (bmask[j] >> issue_phase) & 1u;
+      dma16(ok ? bptr[j] + (long long)c * L.b_step : zero, stage + PART + (64 * (4 * j + wave)) * 16);
+    }
+  };
+  auto issue_done = [&]() { issue_phase = issue_phase + 1 == L.period ? 0 : issue_phase + 1; };
+
+  f32x16 acc[FA][FB];
+#pragma unroll
+  for (int i = 0; i < FA; ++i)
+#pragma unroll
+    for (int j = 0; j < FB; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // ---- operand reads: lane group g = lane >> 4 takes channels 16*(g&1).. of a 32-channel block and pixels
+  //      8*(g>>1) .. +7 of the 16-pixel step (two transposing reads of 4 pixels each) ----
+  int boff[FB], aoff[FA];   // byte offset inside a tile of a 32-channel block, step 0 of this wave's pixel half
+  {
+    const int g = lane >> 4, i16 = lane & 15;
+    const int prow = 32 * wk + 8 * (g >> 1) + (i16 >> 2);
+    const int x = 2 * ((i16 >> 2) & 3);
+#pragma unroll
+    for (int f = 0; f < FB; ++f) boff[f] = prow * ROWB + (i16 & 3) * 8 + (((2 * f + (g & 1)) ^ x) * 32);
+#pragma unroll
+    for (int f = 0; f < FA; ++f) aoff[f] = prow * ROWB + (i16 & 3) * 8 + (((2 * (FA * wave_m + f) + (g & 1)) ^ x) * 32);
+  }
+  // fragment f < FA: dy block 2*wave_m.. (rows of D); f >= FA: x block f - FA (columns of D).
+  // The transposing read is issued as inline assembly: the compiler treats its builtin as a possible LDS
+  // store and puts a wait for ALL outstanding direct-to-LDS loads in front of every one of them, which
+  // serialises the pipeline.  So the waits are explicit here: wait_frags() ties an lgkmcnt(0) to the registers
+  // of a fragment set, and landing of the loads is covered by the vmcnt wait before each barrier.
+  const unsigned lds0 = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)smem);
+  v4s16 flo[2][NF], fhi[2][NF];
+  auto read_one = [&](auto set_tag, auto idx_tag, int c, int ks) {
+    constexpr int S = decltype(set_tag)::value, IDX = decltype(idx_tag)::value;
+    constexpr int F = IDX >> 1, H = IDX & 1;
+    int off;
+    if constexpr (F < FA) off = aoff[F]; else off = PART + boff[F - FA];
+    const unsigned addr = lds0 + (unsigned)(c % STAGES) * (2 * PART) + off + ks * 16 * ROWB;
+    v4s16& v = H == 0 ? flo[S][F] : fhi[S][F];
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "i"(H * 4 * ROWB));
+  };
+  auto wait_frags = [&](auto set_tag) {
+    constexpr int S = decltype(set_tag)::value;
+    static_assert(NF == 6, "operand list below");
+    v4s16 &l0 = flo[S][0], &h0 = fhi[S][0], &l1 = flo[S][1], &h1 = fhi[S][1], &l2 = flo[S][2], &h2 = fhi[S][2];
+    v4s16 &l3 = flo[S][3], &h3 = fhi[S][3], &l4 = flo[S][4], &h4 = fhi[S][4], &l5 = flo[S][5], &h5 = fhi[S][5];
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(l0), "+v"(h0), "+v"(l1), "+v"(h1), "+v"(l2), "+v"(h2), "+v"(l3), "+v"(h3), "+v"(l4), "+v"(h4),
+                   "+v"(l5), "+v"(h5));
+  };
+  auto frag = [&](auto set_tag, int f) {
+    constexpr int S = decltype(set_tag)::value;
+    typedef short v8s16 __attribute__((ext_vector_type(8)));
+    const v8s16 both = __builtin_shufflevector(flo[S][f], fhi[S][f], 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, both);
+  };
+  auto mma_one = [&](auto set_tag, auto k_tag) {
+    constexpr int K = decltype(k_tag)::value;
+    acc[K / FB][K % FB] = mfma32(frag(set_tag, K / FB), frag(set_tag, FA + K % FB), acc[K / FB][K % FB]);
+  };
+
+  // prologue: chunks 0 .. STAGES-2 in flight, chunk 0 visible, the fragments of its first step in set 0
+#pragma unroll
+  for (int p = 0; p < STAGES - 1; ++p)
+    if (p < n) {
+#pragma unroll
+      for (int d = 0; d < NJ; ++d) issue_one(d, p);
+      issue_done();
+    }
+  if (n >= STAGES - 1) wait_vmcnt<(STAGES - 2) * NJ>();
+  else if (n == 2) wait_vmcnt<NJ>();
+  else wait_vmcnt<0>();
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  using set0 = std::integral_constant<int, 0>;
+  using set1 = std::integral_constant<int, 1>;
+  static_for<2 * NF>([&](auto idx) { read_one(set0{}, idx, 0, 0); });
+
+  // One chunk = two half steps of NM (MFMA, piece) slots.  First half: MFMAs of set 0, reads of the second
+  // step into set 1.  Second half: MFMAs of set 1; after slot 1 barrier c+1 (chunk c+1 visible; everybody done
+  // reading chunk c-1), then the first-step reads of chunk c+1 into set 0 and the loads of chunk c+STAGES-1
+  // (into the stage of chunk c-1).  AHEAD = chunks issued beyond c+1 when the barrier is reached.
+  static_assert(2 * NF <= 2 * (NM - 2) && NJ <= 2 * (NM - 2), "slots of a half step");
+  auto step = [&](auto next_tag, auto issue_tag, auto ahead_tag, int c) {
+    constexpr bool NEXT = decltype(next_tag)::value, ISSUE = decltype(issue_tag)::value;
+    constexpr int AHEAD = decltype(ahead_tag)::value;
+    wait_frags(set0{});
+    static_for<NM>([&](auto k) {
+      constexpr int K = decltype(k)::value;
+      mma_one(set0{}, k);
+      if constexpr (2 * K < 2 * NF) {
+        read_one(set1{}, std::integral_constant<int, 2 * K>{}, c, 1);
+        read_one(set1{}, std::integral_constant<int, 2 * K + 1>{}, c, 1);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    wait_frags(set1{});
+    static_for<NM>([&](auto k) {
+      constexpr int K = decltype(k)::value;
+      mma_one(set1{}, k);
+      if constexpr (NEXT) {
+        if constexpr (K == 1) {
+          wait_vmcnt<AHEAD * NJ>();
+          asm volatile("" ::: "memory");
+          __builtin_amdgcn_s_barrier();
+          asm volatile("" ::: "memory");
+        }
+        if constexpr (K >= 2 && 2 * (K - 2) < 2 * NF) {
+          read_one(set0{}, std::integral_constant<int, 2 * (K - 2)>{}, c + 1, 0);
+          read_one(set0{}, std::integral_constant<int, 2 * (K - 2) + 1>{}, c + 1, 0);
+        }
+      }
+      if constexpr (ISSUE && K >= 2) {
+        // NJ pieces over the NM - 2 slots after the barrier
+        constexpr int PER = (NJ + NM - 3) / (NM - 2);
+#pragma unroll
+        for (int d = (K - 2) * PER; d < (K - 1) * PER && d < NJ; ++d) issue_one(d, c + STAGES - 1);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    if constexpr (ISSUE) issue_done();
+  };
+  using yes = std::true_type;
+  using no = std::false_type;
+  {
+    int c = 0;
+    for (; c + STAGES - 1 < n; ++c) step(yes{}, yes{}, std::integral_constant<int, STAGES - 3>{}, c);
+    // tail: nothing left to issue; chunks beyond c+1 still in flight: n - c - 2
+    static_for<STAGES - 2>([&](auto r_tag) {
+      constexpr int AH = STAGES - 3 - decltype(r_tag)::value;   // STAGES-3, ..., 0
+      if (c + 1 < n && n - c - 2 == AH) {
+        step(yes{}, no{}, std::integral_constant<int, AH>{}, c);
+        ++c;
+      }
+    });
+    step(no{}, no{}, std::integral_constant<int, 0>{}, c);   // c == n - 1
+  }
+
+  // ---- add the two pixel halves: wave (wave_m, wk) keeps block row wk of its two and receives its partner's ----
+  wait_vmcnt<0>();
+  __syncthreads();
+  f32x4* mine = reinterpret_cast<f32x4*>(smem) + (size_t)wave * 1024;
+  const f32x4* theirs = reinterpret_cast<const f32x4*>(smem) + (size_t)(wave ^ 2) * 1024;
+  f32x16 keep[FB];
+#pragma unroll
+  for (int j = 0; j < FB; ++j) {
+    const f32x16 give = wk == 0 ? acc[1][j] : acc[0][j];
+    keep[j] = wk == 0 ? acc[0][j] : acc[1][j];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      mine[(j * 4 + g) * 64 + lane] = f32x4{give[4 * g], give[4 * g + 1], give[4 * g + 2], give[4 * g + 3]};
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < FB; ++j)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const f32x4 p = theirs[(j * 4 + g) * 64 + lane];
+      keep[j][4 * g] += p[0]; keep[j][4 * g + 1] += p[1]; keep[j][4 * g + 2] += p[2]; keep[j][4 * g + 3] += p[3];
+    }
+  // D block: lane holds column ci = 32 j + (lane & 31), rows co = 8 (v >> 2) + 4 (lane >> 5) + (v & 3) of the block row
+  float* dst = L.partial ? L.partial + (size_t)split * L.split_stride : a.dw;
+  const int mode = L.partial ? 0 : (L.splits > 1 ? 1 : 2);   // store / atomic add / owned read-modify-write
+  const int ntaps = a.ntaps, Ci = a.Ci;
+  const int co_base = co0 + 64 * wave_m + 32 * wk + 4 * (lane >> 5);
+#pragma unroll
+  for (int j = 0; j < FB; ++j) {
+    const int ci = ci0 + 32 * j + (lane & 31);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int co = co_base + 8 * (v >> 2) + (v & 3);
+      float* o = dst + ((size_t)co * ntaps + tapi) * Ci + ci;
+      const float val = keep[j][v];
+      if (mode == 0) *o = val;
+      else if (mode == 1) atomicAdd(o, val);
+      else *o += val;
+    }
+  }
+}
+
+bool conv_wgrad128_applies(const WgradArgs& a) {
+  if (a.Co % 128 != 0 || a.Ci % 128 != 0 || a.Cx != a.Ci || a.ntaps < 1) return false;
+  if (a.OW < 1 || 64 % a.OW != 0 || (a.N * a.OH * a.OW) % 64 != 0 || a.OH > 32) return false;
+  return a.Hi == a.stride * a.OH;
+}
+
+hipError_t launch_conv_wgrad128(const WgradArgs& a, hipStream_t s) {
+  if (!conv_wgrad128_applies(a) || a.N * a.OH * a.OW <= 0) return hipErrorInvalidValue;
+  constexpr int STAGES = 5;   // 5 x 32 KB: all of the LDS
+  constexpr size_t lds = (size_t)STAGES * 2 * 64 * 256;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad128_kernel<STAGES>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int total_chunks = a.N * a.OH * a.OW / 64;
+  Wgrad128Launch L;
+  L.co_tiles = a.Co / 128;
+  L.ci_tiles = a.Ci / 128;
+  const int tiles = L.co_tiles * L.ci_tiles * a.ntaps;
+  const size_t elems = (size_t)a.Co * a.ntaps * a.Ci;
+  // pixel splits only when the blocks alone leave most compute units idle, and only through scratch
+  const int max_by_scratch = a.scratch ? (int)(a.scratch_bytes / (elems * 4)) : 0;
+  int S = 1;
+  if (tiles <= 128 && max_by_scratch >= 2) {
+    S = 256 / tiles;
+    if (S > max_by_scratch) S = max_by_scratch;
+    if (S > total_chunks / 8) S = total_chunks / 8;
+    if (S < 1) S = 1;
+  }
+  L.chunks_per_split = (total_chunks + S - 1) / S;
+  L.splits = (total_chunks + L.chunks_per_split - 1) / L.chunks_per_split;
+  L.partial = L.splits > 1 ? a.scratch : nullptr;
+  L.split_stride = elems;
+  const int d_oh_full = 64 / a.OW;
+  L.d_oh = d_oh_full % a.OH;
+  int g = L.d_oh == 0 ? a.OH : L.d_oh, h = a.OH;   // gcd(d_oh, OH)
+  while (h) { const int r = g % h; g = h; h = r; }
+  L.period = a.OH / g;
+  L.a_step = (long long)64 * a.Co * 2;
+  L.b_step = (long long)d_oh_full * a.stride * a.Wi * a.Cx * 2;
+  hipLaunchKernelGGL((conv_wgrad128_kernel<STAGES>), dim3(tiles * L.splits), dim3(256), lds, s, a, L);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || !L.partial) return e;
+  const size_t n4 = elems / 4;
+  size_t blocks = (n4 + 255) / 256;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, s, reinterpret_cast<float4*>(a.dw),
+                     reinterpret_cast<const float4*>(a.scratch), n4, L.splits, elems / 4);
+  return hipGetLastError();
+}
+
 bool conv_wgrad_wide_applies(const WgradArgs& a) {
   return a.Co % 160 == 0 && a.Ci % 160 == 0 && a.Cx == a.Ci && a.OW >= 1 && 64 % a.OW == 0 && a.ntaps >= 1;
 }
