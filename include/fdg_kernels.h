@@ -44,14 +44,17 @@ int fdgk_conv_dgrad(const void* dy_b16, const void* wt_b16, const float* addend_
                     float* dx_f32, void* dx_b16, int n, int h, int w, int ci, int co, int ksize, int stride,
                     void* hip_stream);
 
-/* Weight gradient, the adjoint in w, ACCUMULATED into dw_f32 [co][ksize*ksize][ci] with fp32 atomics
- * (zero it first):  dw[o,r,q,i] += sum_{n,ho,wo} dy[n,ho,wo,o] * x[n, ho*s+r-p, wo*s+q-p, i].
- * The pixel dimension is split over workgroups.  With scratch_f32 (DEVICE memory, scratch_bytes long,
- * 16-byte aligned, contents irrelevant, may be NULL) the splits store partial arrays there and a second
- * kernel adds them; without it they add with atomics.  fdgk_conv_wgrad_scratch_bytes returns the size that
- * is useful for a shape (0 if the shape never uses scratch).                                          */
+/* Weight gradient, the adjoint in w, into dw_f32 [co][ksize*ksize][ci]:
+ *   dw[o,r,q,i] (+)= sum_{n,ho,wo} dy[n,ho,wo,o] * x[n, ho*s+r-p, wo*s+q-p, i].
+ * overwrite == 0: the sum is ADDED to dw (zero it first for the plain gradient); overwrite != 0: dw is
+ * written, whatever it held before.  The pixel dimension may be split over workgroups.  With scratch_f32
+ * (DEVICE memory, scratch_bytes long, 16-byte aligned, contents irrelevant, may be NULL) the splits store
+ * partial arrays there and a second kernel adds them; without it they add with fp32 atomics.
+ * fdgk_conv_wgrad_scratch_bytes returns the size that is useful for a shape (0 if the shape never uses
+ * scratch).                                                                                            */
 size_t fdgk_conv_wgrad_scratch_bytes(int n, int h, int w, int ci, int co, int ksize, int stride);
 int fdgk_conv_wgrad(const void* x_b16, const void* dy_b16, float* dw_f32, float* scratch_f32, size_t scratch_bytes,
+                    int overwrite,
                     int n, int h, int w, int ci, int co, int ksize, int stride, void* hip_stream);
 
 /* Training-mode batch normalisation over the m rows of x_b16 [m, c].

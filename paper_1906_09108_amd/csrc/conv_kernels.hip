@@ -331,6 +331,10 @@ hipError_t launch_conv_wgrad(const WgradArgs& a, hipStream_t s) {
   static const bool old_wide = getenv("FDG_WGRAD_160") != nullptr;   // A/B switch for measurements
   if (conv_wgrad128_applies(a) && !(old_wide && conv_wgrad_wide_applies(a))) return launch_conv_wgrad128(a, s);
   if (conv_wgrad_wide_applies(a)) return launch_conv_wgrad_wide(a, s);
+  if (a.overwrite) {   // the kernels below only add (atomics)
+    hipError_t e = launch_fill_f32(a.dw, (size_t)a.Co * a.ntaps * a.Ci, 0.f, s);
+    if (e != hipSuccess) return e;
+  }
   if (a.Co <= 64 && a.Cx <= 64) return run_wgrad<32, 32, 1, 1, 4>(a, s);
   return run_wgrad<128, 128, 2, 2, 1>(a, s);
 }
@@ -409,9 +413,10 @@ size_t conv_wgrad_scratch_bytes(const ConvShape& c) {
 }
 
 hipError_t conv_wgrad(const ConvShape& c, const bf16_t* x, const bf16_t* dy, float* dw, float* scratch,
-                      size_t scratch_bytes, hipStream_t s) {
+                      size_t scratch_bytes, bool overwrite, hipStream_t s) {
   WgradArgs a{};
   a.dy = dy; a.x = x; a.dw = dw; a.scratch = scratch; a.scratch_bytes = scratch_bytes;
+  a.overwrite = overwrite ? 1 : 0;
   a.N = c.N; a.OH = c.Ho(); a.OW = c.Wo(); a.Co = c.Co;
   a.Hi = c.Hi; a.Wi = c.Wi; a.Cx = c.Cip; a.Ci = c.Ci;
   a.stride = c.stride; a.ntaps = c.T;

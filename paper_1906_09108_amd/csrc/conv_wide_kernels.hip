@@ -608,11 +608,11 @@ __global__ __launch_bounds__(256) void conv_wgrad_dma_kernel(WgradArgs a, WgradW
     }
 }
 
-// dw += sum over splits of the partial arrays
+// dw (+)= sum over splits of the partial arrays
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(float4* __restrict__ dw, const float4* __restrict__ partial,
-                                                           size_t n4, int splits, size_t stride4) {
+                                                           size_t n4, int splits, size_t stride4, int overwrite) {
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
-    float4 s = dw[i];
+    float4 s = overwrite ? make_float4(0.f, 0.f, 0.f, 0.f) : dw[i];
     for (int k = 0; k < splits; ++k) {
       const float4 p = partial[(size_t)k * stride4 + i];
       s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
@@ -704,7 +704,10 @@ __global__ __launch_bounds__(256) void conv_wgrad128_kernel(WgradArgs a, Wgrad12
     } else {
       const int j = d - JP;
       const bool ok = (bmask[j] >> issue_phase) & 1u;
-      dma16(ok ? bptr[j] + (long long)c * L.b_step : zero, stage + PART + (64 * (4 * j + wave)) * 16);
+      // select per 32-bit half: two conditional moves instead of a branch around the address computation
+      const uint64_t pa = (uint64_t)(bptr[j] + (long long)c * L.b_step), pz = (uint64_t)zero;
+      const uint32_t lo = ok ? (uint32_t)pa : (uint32_t)pz, hi = ok ? (uint32_t)(pa >> 32) : (uint32_t)(pz >> 32);
+      dma16((const char*)(((uint64_t)hi << 32) | lo), stage + PART + (64 * (4 * j + wave)) * 16);
     }
   };
   auto issue_done = [&]() { issue_phase = issue_phase + 1 == L.period ? 0 : issue_phase + 1; };
@@ -738,21 +741,31 @@ __global__ __launch_bounds__(256) void conv_wgrad128_kernel(WgradArgs a, Wgrad12
   v4s16 flo[2][NF], fhi[2][NF];
   auto read_one = [&](auto set_tag, auto idx_tag, int c, int ks) {
     constexpr int S = decltype(set_tag)::value, IDX = decltype(idx_tag)::value;
-    constexpr int F = IDX >> 1, H = IDX & 1;
+    // issue order = the order the MFMAs need them: A0, B0, B1, B2, B3, A1
+    constexpr int POS = IDX >> 1, H = IDX & 1;
+    constexpr int F = POS == 0 ? 0 : (POS == NF - 1 ? 1 : POS + 1);
     int off;
     if constexpr (F < FA) off = aoff[F]; else off = PART + boff[F - FA];
     const unsigned addr = lds0 + (unsigned)(c % STAGES) * (2 * PART) + off + ks * 16 * ROWB;
     v4s16& v = H == 0 ? flo[S][F] : fhi[S][F];
     asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "i"(H * 4 * ROWB));
   };
-  auto wait_frags = [&](auto set_tag) {
-    constexpr int S = decltype(set_tag)::value;
-    static_assert(NF == 6, "operand list below");
-    v4s16 &l0 = flo[S][0], &h0 = fhi[S][0], &l1 = flo[S][1], &h1 = fhi[S][1], &l2 = flo[S][2], &h2 = fhi[S][2];
-    v4s16 &l3 = flo[S][3], &h3 = fhi[S][3], &l4 = flo[S][4], &h4 = fhi[S][4], &l5 = flo[S][5], &h5 = fhi[S][5];
-    asm volatile("s_waitcnt lgkmcnt(0)"
-                 : "+v"(l0), "+v"(h0), "+v"(l1), "+v"(h1), "+v"(l2), "+v"(h2), "+v"(l3), "+v"(h3), "+v"(l4), "+v"(h4),
-                   "+v"(l5), "+v"(h5));
+  // LDS reads return in order, so "the first m reads of this set have landed" is lgkmcnt <= (reads of the set
+  // still to come) + (reads of the other set issued meanwhile).  before_mma(set, K, N) states that for MFMA K
+  // and ties the wait to the registers that become valid, so the MFMA cannot move above it.
+  auto before_mma = [&](auto set_tag, auto k_tag, auto n_tag) {
+    constexpr int S = decltype(set_tag)::value, K = decltype(k_tag)::value, N = decltype(n_tag)::value;
+    static_assert(FA == 2 && FB == 4 && N >= 0 && N <= 15, "fragment order A0 B0 B1 B2 B3 A1");
+    if constexpr (K == 0) {
+      v4s16 &l0 = flo[S][0], &h0 = fhi[S][0], &l1 = flo[S][FA], &h1 = fhi[S][FA];
+      asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(l0), "+v"(h0), "+v"(l1), "+v"(h1) : "n"(N));
+    } else if constexpr (K >= 1 && K <= 3) {
+      v4s16 &l0 = flo[S][FA + K], &h0 = fhi[S][FA + K];
+      asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(l0), "+v"(h0) : "n"(N));
+    } else if constexpr (K == 4) {
+      v4s16 &l0 = flo[S][1], &h0 = fhi[S][1];
+      asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(l0), "+v"(h0) : "n"(N));
+    }
   };
   auto frag = [&](auto set_tag, int f) {
     constexpr int S = decltype(set_tag)::value;
@@ -791,9 +804,10 @@ __global__ __launch_bounds__(256) void conv_wgrad128_kernel(WgradArgs a, Wgrad12
   auto step = [&](auto next_tag, auto issue_tag, auto ahead_tag, int c) {
     constexpr bool NEXT = decltype(next_tag)::value, ISSUE = decltype(issue_tag)::value;
     constexpr int AHEAD = decltype(ahead_tag)::value;
-    wait_frags(set0{});
     static_for<NM>([&](auto k) {
       constexpr int K = decltype(k)::value;
+      // 12 reads per set, two per slot: set 1 is filled in slots 0..5 of this half
+      before_mma(set0{}, k, std::integral_constant<int, 8>{});
       mma_one(set0{}, k);
       if constexpr (2 * K < 2 * NF) {
         read_one(set1{}, std::integral_constant<int, 2 * K>{}, c, 1);
@@ -801,9 +815,12 @@ __global__ __launch_bounds__(256) void conv_wgrad128_kernel(WgradArgs a, Wgrad12
       }
       __builtin_amdgcn_sched_barrier(0);
     });
-    wait_frags(set1{});
     static_for<NM>([&](auto k) {
       constexpr int K = decltype(k)::value;
+      // set 0 of the next chunk is filled in slots 2..7 of this half (only when there is a next chunk)
+      constexpr int LEFT = K == 0 ? 8 : (K == 1 ? 6 : (K == 2 ? 4 : (K == 3 ? 2 : 0)));
+      constexpr int NEWER = (NEXT && K > 2) ? 2 * (K - 2) : 0;
+      before_mma(set1{}, k, std::integral_constant<int, (K <= 4 ? LEFT + NEWER : 15)>{});
       mma_one(set1{}, k);
       if constexpr (NEXT) {
         if constexpr (K == 1) {
@@ -867,7 +884,7 @@ __global__ __launch_bounds__(256) void conv_wgrad128_kernel(WgradArgs a, Wgrad12
     }
   // D block: lane holds column ci = 32 j + (lane & 31), rows co = 8 (v >> 2) + 4 (lane >> 5) + (v & 3) of the block row
   float* dst = L.partial ? L.partial + (size_t)split * L.split_stride : a.dw;
-  const int mode = L.partial ? 0 : (L.splits > 1 ? 1 : 2);   // store / atomic add / owned read-modify-write
+  const int mode = (L.partial || (L.splits == 1 && a.overwrite)) ? 0 : (L.splits > 1 ? 1 : 2);   // store / atomic add / owned read-modify-write
   const int ntaps = a.ntaps, Ci = a.Ci;
   const int co_base = co0 + 64 * wave_m + 32 * wk + 4 * (lane >> 5);
 #pragma unroll
@@ -935,7 +952,7 @@ hipError_t launch_conv_wgrad128(const WgradArgs& a, hipStream_t s) {
   size_t blocks = (n4 + 255) / 256;
   if (blocks > 2048) blocks = 2048;
   hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, s, reinterpret_cast<float4*>(a.dw),
-                     reinterpret_cast<const float4*>(a.scratch), n4, L.splits, elems / 4);
+                     reinterpret_cast<const float4*>(a.scratch), n4, L.splits, elems / 4, a.overwrite);
   return hipGetLastError();
 }
 
@@ -984,6 +1001,10 @@ hipError_t launch_conv_wgrad_wide(const WgradArgs& a, hipStream_t s) {
   const bool use_partial = max_by_scratch >= 2 && L.splits > 1;
   L.partial = use_partial ? a.scratch : nullptr;
   L.split_stride = elems;
+  if (a.overwrite && !use_partial) {   // the atomics path only adds
+    hipError_t e = launch_fill_f32(a.dw, elems, 0.f, s);
+    if (e != hipSuccess) return e;
+  }
   hipLaunchKernelGGL((conv_wgrad_dma_kernel<STAGES>), dim3(tiles * L.splits), dim3(256), lds, s, a, L);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || !use_partial) return e;
@@ -991,7 +1012,7 @@ hipError_t launch_conv_wgrad_wide(const WgradArgs& a, hipStream_t s) {
   size_t blocks = (n4 + 255) / 256;
   if (blocks > 2048) blocks = 2048;
   hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, s, reinterpret_cast<float4*>(a.dw),
-                     reinterpret_cast<const float4*>(a.scratch), n4, L.splits, elems / 4);
+                     reinterpret_cast<const float4*>(a.scratch), n4, L.splits, elems / 4, a.overwrite);
   return hipGetLastError();
 }
 

@@ -49,6 +49,7 @@ struct WgradArgs {
   int tap[9];        // pack_tap(dh, dw, 0)
   float* scratch;    // optional device scratch for split partial sums (see conv_wgrad_scratch_bytes)
   size_t scratch_bytes;
+  int overwrite;     // 1: dw = sum (no need to zero dw first);  0: dw += sum
 };
 hipError_t launch_conv_wgrad(const WgradArgs& a, hipStream_t s);
 
@@ -67,11 +68,12 @@ hipError_t conv_forward(const ConvShape& c, const bf16_t* x, const bf16_t* w, co
 // dx[N,Hi,Wi,Cip] = conv^T(dy[N,Ho,Wo,Co], wt[Cip][T][Co]) (+ addend, optionally only where addmask > 0)
 hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                       const bf16_t* addmask, float* out_f32, bf16_t* out_b16, hipStream_t s);
-// dw[Co][T][Ci] += sum over pixels of dy * x   (fp32 atomics)
+// dw[Co][T][Ci] (+)= sum over pixels of dy * x.  overwrite = false: accumulated into dw (fp32 atomics where the
+// pixel dimension is split), dw zeroed by the caller;  overwrite = true: dw is written, whatever it held.
 // scratch (optional): device memory for the partial sums of the pixel splits; without it they are added
 // with atomics.  conv_wgrad_scratch_bytes gives the useful size for a shape (0: the shape never uses it).
 hipError_t conv_wgrad(const ConvShape& c, const bf16_t* x, const bf16_t* dy, float* dw, float* scratch,
-                      size_t scratch_bytes, hipStream_t s);
+                      size_t scratch_bytes, bool overwrite, hipStream_t s);
 size_t conv_wgrad_scratch_bytes(const ConvShape& c);
 
 // Batch-norm pieces on [M, C] NHWC tensors (C % 8 == 0, C <= 2048).

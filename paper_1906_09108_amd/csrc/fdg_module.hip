@@ -236,7 +236,7 @@ bool build_plan(const fdg_module_desc* desc, Plan& p, fdg_status* why) {
   p.o_params = take(p.P * 4);
   p.o_mom = take(p.P * 4);
   p.o_grads = take(p.P * 4);
-  p.o_bsums = take(p.stat_floats * 4);     // directly after the gradients: one fill clears both
+  p.o_bsums = take(p.stat_floats * 4);
   p.o_running = take(p.stat_floats * 4);
   p.o_table = take(p.convs.size() * sizeof(WeightEmitEntry));
   {  // one slot
@@ -388,7 +388,7 @@ hipError_t mconv_wgrad(const fdg_module* m, const ConvInfo& c, const bf16_t* x, 
   const double bytes = 2 * conv_in_elems(c.sh) + 2 * conv_out_elems(c.sh) + 4.0 * c.sh.Co * c.sh.T * c.sh.Ci;
   ProfScope ps(m, PC_CONV_WGRAD, conv_flops(c.sh), bytes, s);
   return conv_wgrad(c.sh, x, dy, m->grads() + c.p_off, reinterpret_cast<float*>(m->ws + m->p.o_wscratch),
-                    m->p.wscratch_bytes, s);
+                    m->p.wscratch_bytes, /*overwrite=*/true, s);
 }
 
 hipError_t bn_stats(const SlotView& v, const BnInfo& b, const bf16_t* x, hipStream_t s) {
@@ -597,8 +597,9 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
   m->last_stream = s;
   SlotView v{m, m->slot(m->seq_bwd)};  // the OLDEST saved forward
   const int N = p.d.n;
-  // gradients and backward sums start at zero (weight gradients accumulate with atomics)
-  FDG_TRY(launch_fill_zero(m->ws + p.o_grads, p.o_running - p.o_grads, s));
+  // the backward sums of batch norm accumulate with atomics and start at zero; every gradient is written
+  // (not accumulated) by the kernel that produces it
+  FDG_TRY(launch_fill_zero(m->ws + p.o_bsums, p.o_running - p.o_bsums, s));
   int cur = 0;
   if (!p.is_top)  // gradient shrinking of Eq. 15: multiply by beta before anything else
     FDG_TRY(launch_nchw_to_nhwc(grad_out_dev, m->G(cur), m->GB(cur), N, p.out_c, p.out_h * p.out_w, p.out_c, p.d.beta, s));

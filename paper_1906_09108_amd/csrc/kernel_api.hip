@@ -41,11 +41,12 @@ size_t fdgk_conv_wgrad_scratch_bytes(int n, int h, int w, int ci, int co, int ks
 }
 
 int fdgk_conv_wgrad(const void* x_b16, const void* dy_b16, float* dw_f32, float* scratch_f32, size_t scratch_bytes,
+                    int overwrite,
                     int n, int h, int w, int ci, int co, int ksize, int stride, void* hip_stream) {
   ConvShape c;
   if (!x_b16 || !dy_b16 || !dw_f32 || !conv_shape(c, n, h, w, ci, co, ksize, stride)) return (int)hipErrorInvalidValue;
   return (int)conv_wgrad(c, static_cast<const bf16_t*>(x_b16), static_cast<const bf16_t*>(dy_b16), dw_f32, scratch_f32,
-                         scratch_bytes, st(hip_stream));
+                         scratch_bytes, overwrite != 0, st(hip_stream));
 }
 
 int fdgk_bn_stats(const void* x_b16, float* sums_f32, int m, int c, void* hip_stream) {

@@ -18,7 +18,7 @@ def _lib():
         vp, i, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
         lib.fdgk_conv_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
         lib.fdgk_conv_dgrad.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
-        lib.fdgk_conv_wgrad.argtypes = [vp, vp, vp, vp, sz, i, i, i, i, i, i, i, vp]
+        lib.fdgk_conv_wgrad.argtypes = [vp, vp, vp, vp, sz, i, i, i, i, i, i, i, i, vp]
         lib.fdgk_conv_wgrad_scratch_bytes.argtypes = [i, i, i, i, i, i, i]
         lib.fdgk_bn_stats.argtypes = [vp, vp, i, i, vp]
         lib.fdgk_bn_apply.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, f, i, vp]
@@ -50,10 +50,11 @@ def fdgk_conv_wgrad_scratch_bytes(n, h, w, ci, co, ksize, stride) -> int:
     return int(_lib().fdgk_conv_wgrad_scratch_bytes(n, h, w, ci, co, ksize, stride))
 
 
-def fdgk_conv_wgrad(x_b16, dy_b16, dw_f32, scratch_f32, n, h, w, ci, co, ksize, stride, stream=None):
-    """scratch_f32: a float32 CUDA tensor (any contents) or None."""
+def fdgk_conv_wgrad(x_b16, dy_b16, dw_f32, scratch_f32, n, h, w, ci, co, ksize, stride, overwrite=False, stream=None):
+    """scratch_f32: a float32 CUDA tensor (any contents) or None.  overwrite: write dw instead of adding to it."""
     nbytes = 0 if scratch_f32 is None else scratch_f32.numel() * scratch_f32.element_size()
-    _ok(_lib().fdgk_conv_wgrad(_ptr(x_b16), _ptr(dy_b16), _ptr(dw_f32), _ptr(scratch_f32), nbytes, n, h, w, ci, co,
+    _ok(_lib().fdgk_conv_wgrad(_ptr(x_b16), _ptr(dy_b16), _ptr(dw_f32), _ptr(scratch_f32), nbytes, int(bool(overwrite)),
+                               n, h, w, ci, co,
                                ksize, stride, _stream_handle(stream)), "fdgk_conv_wgrad")
 
 

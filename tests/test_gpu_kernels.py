@@ -169,6 +169,14 @@ def test_conv_wgrad(case):
         t.cuda.synchronize()
         got = dw2.cpu().numpy().reshape(co, k, k, ci).transpose(0, 3, 1, 2) - 1.0
         assert rel(got, ref) <= F32_TOL
+    else:
+        scratch = None
+    for scr in (None, scratch):                                                     # overwrite: prior contents do not count
+        dw3 = t.full((co, k * k, ci), 7.0, dtype=t.float32, device="cuda")
+        K.fdgk_conv_wgrad(xd, dyd, dw3, scr, n, h, w, ci, co, k, s, overwrite=True)
+        t.cuda.synchronize()
+        got = dw3.cpu().numpy().reshape(co, k, k, ci).transpose(0, 3, 1, 2)
+        assert rel(got, ref) <= F32_TOL
 
 
 BN_CASES = [(189, 16), (4096, 16), (1000, 40), (512, 640), (16384, 32), (77, 2048)]
