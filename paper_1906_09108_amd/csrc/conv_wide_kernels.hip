@@ -284,7 +284,13 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
   // NM (MFMA, piece of other work) pairs pinned with scheduling barriers.
   constexpr int NM = FN * FM, NFRAG = FN + FM;
   static_assert(NFRAG + 2 <= NM && 2 + JW < NM, "slots of a half step");
-  bf16x8 fa[2][FN], fb[2][FM];
+  // The reads are inline assembly with explicit waits: left to the compiler every half step would begin with a
+  // wait for ALL outstanding LDS reads, the ones issued a moment ago included, which exposes the LDS latency
+  // twice per step.  LDS reads return in order, so "the first m fragments of this set have landed" is
+  // lgkmcnt <= (fragments of the set still to come) + (fragments of the other set issued meanwhile).
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 fa[2][FN], fb[2][FM];
+  const unsigned lds0 = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)smem);
   // fragment idx of a half step in the order the MFMAs need them: B0, A0, B1, A1, A2, ...
   auto read_one = [&](auto set_tag, auto idx_tag, int wslot, int xbuf, auto tap_tag, int ss) {
     constexpr int S = decltype(set_tag)::value, IDX = decltype(idx_tag)::value, T = decltype(tap_tag)::value;
@@ -295,15 +301,38 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
       const int p = prow[f] + tdh[T] * W + tdw[T];
       const bool ok = (unsigned)(poh[f] + tdh[T]) < (unsigned)H && (unsigned)(pow_[f] + tdw[T]) < (unsigned)W;
       const int off = ok ? xbuf * XBYTES + p * ROWB : ZOFF + (p & 1) * ROWB;
-      fb[S][f] = *reinterpret_cast<const bf16x8*>(smem + off + ((u ^ ((p >> 1) & 7)) << 4));
+      u32x4& dst = fb[S][f];
+      const unsigned addr = lds0 + off + ((u ^ ((p >> 1) & 7)) << 4);
+      asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(addr));
     } else {
       constexpr int f = IDX == 1 ? 0 : IDX - 2;
-      fa[S][f] = *reinterpret_cast<const bf16x8*>(smem + 2 * XBYTES + wslot * WBYTES + wrow_off[f] + ((u ^ wrow_swz[f]) << 4));
+      u32x4& dst = fa[S][f];
+      const unsigned addr = lds0 + 2 * XBYTES + wslot * WBYTES + wrow_off[f] + ((u ^ wrow_swz[f]) << 4);
+      asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(addr));
     }
   };
+  // Before MFMA K (K = 2 i + j uses A_i and B_j): the fragments it is the first to use have landed when at
+  // most N reads are outstanding; the wait is tied to their registers so that the MFMA cannot move above it.
+  auto before_mma = [&](auto set_tag, auto k_tag, auto n_tag) {
+    constexpr int S = decltype(set_tag)::value, K = decltype(k_tag)::value, N = decltype(n_tag)::value;
+    static_assert(N >= 0 && N <= 15, "lgkmcnt range");
+    if constexpr (K == 0) {
+      u32x4 &r0 = fb[S][0], &r1 = fa[S][0];
+      asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(r0), "+v"(r1) : "n"(N));
+    } else if constexpr (K == 1) {
+      u32x4& r0 = fb[S][1];
+      asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(r0) : "n"(N));
+    } else if constexpr (K % 2 == 0) {
+      u32x4& r0 = fa[S][K / 2];
+      asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(r0) : "n"(N));
+    }
+  };
+  // fragments of a set not yet needed when MFMA K starts
+  auto left_after = [](int K) constexpr { return (FN + 2) - (K == 0 ? 2 : (K == 1 ? 3 : 3 + K / 2)); };
   auto mma_one = [&](auto set_tag, auto k_tag) {
     constexpr int S = decltype(set_tag)::value, K = decltype(k_tag)::value;
-    acc[K / FM][K % FM] = mfma32(fa[S][K / FM], fb[S][K % FM], acc[K / FM][K % FM]);
+    acc[K / FM][K % FM] = mfma32(__builtin_bit_cast(bf16x8, fa[S][K / FM]), __builtin_bit_cast(bf16x8, fb[S][K % FM]),
+                                 acc[K / FM][K % FM]);
   };
   using set0 = std::integral_constant<int, 0>;
   using set1 = std::integral_constant<int, 1>;
@@ -324,6 +353,9 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
       // first half step: MFMAs of set 0, reads of this step's second half into set 1
       static_for<NM>([&](auto k) {
         constexpr int K = decltype(k)::value;
+        // set 1 is filled one fragment per slot from slot 0 on
+        if constexpr (K <= 1 || K % 2 == 0)
+          before_mma(set0{}, k, std::integral_constant<int, left_after(K) + (K < NFRAG ? K : NFRAG)>{});
         mma_one(set0{}, k);
         if constexpr (K < NFRAG) read_one(set1{}, k, slot, c & 1, t_tag, 1);
         __builtin_amdgcn_sched_barrier(0);
@@ -338,6 +370,9 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
       const int kbyte = TT < 9 ? tko[TT < 9 ? TT : 0] + c * 128 : tko[TT < 9 ? 0 : TT - 9] + (c + 1) * 128;
       static_for<NM>([&](auto k) {
         constexpr int K = decltype(k)::value;
+        // set 0 of the next step is filled one fragment per slot from slot 2 on (when there is a next step)
+        if constexpr (K <= 1 || K % 2 == 0)
+          before_mma(set1{}, k, std::integral_constant<int, left_after(K) + ((MORE && K > 2) ? (K - 2 < NFRAG ? K - 2 : NFRAG) : 0)>{});
         mma_one(set1{}, k);
         if constexpr (MORE) {
           if constexpr (K == 1) {
@@ -451,9 +486,14 @@ hipError_t launch_conv_gather_wide(const GatherConvArgs& a, hipStream_t s) {
 // sums are added with fp32 atomics.
 typedef short v4s16 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ bf16x8 lds_read_tr8(const unsigned char* p) {
-  const v4s16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s16*)p);
-  const v4s16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s16*)(p + 16 * 320));
+// Both halves of a fragment as inline assembly, not through the builtin: the compiler treats the builtin as a
+// possible LDS store and makes every one of them wait for ALL outstanding direct-to-LDS loads.  The caller
+// waits (lds_wait_frags) before it uses the values.
+__device__ __forceinline__ void lds_read_tr8(unsigned lds_addr, v4s16& lo, v4s16& hi) {
+  asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(lds_addr));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:5120" : "=v"(hi) : "v"(lds_addr));   // 16 rows of 320 bytes further
+}
+__device__ __forceinline__ bf16x8 join_tr8(v4s16 lo, v4s16 hi) {
   typedef short v8s16 __attribute__((ext_vector_type(8)));
   const v8s16 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(bf16x8, both);
@@ -560,6 +600,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_dma_kernel(WgradArgs a, WgradW
   //   pixel r = 32*ks + 4*(lane>>4) + ((lane&15)>>2), channels cbase + 16*f + 4*(lane&3)
   const int g = lane >> 4, i16 = lane & 15;
   const int r_in_step = 4 * g + (i16 >> 2);
+  const unsigned lds0 = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)smem);
 
 #pragma unroll
   for (int p = 0; p < STAGES - 1; ++p)
@@ -571,17 +612,29 @@ __global__ __launch_bounds__(256) void conv_wgrad_dma_kernel(WgradArgs a, WgradW
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     if (c + STAGES - 1 < nchunks) issue(c + STAGES - 1);
-    const unsigned char* stage = smem + (size_t)(c % STAGES) * (2 * PART);
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
       const int r = 32 * ks + r_in_step;
       const int swz = (r >> 2) & 1;   // the same for r and r + 16
-      bf16x8 fa[F], fb[F];
+      v4s16 alo[F], ahi[F], blo[F], bhi[F];
 #pragma unroll
       for (int f = 0; f < F; ++f) {
         const int slot_a = ((wm * 80 + f * 16) >> 4) ^ swz, slot_b = ((wn * 80 + f * 16) >> 4) ^ swz;
-        fa[f] = lds_read_tr8(stage + r * ROWB + slot_a * 32 + (i16 & 3) * 8);
-        fb[f] = lds_read_tr8(stage + PART + r * ROWB + slot_b * 32 + (i16 & 3) * 8);
+        const unsigned base = lds0 + (unsigned)(c % STAGES) * (2 * PART) + r * ROWB + (i16 & 3) * 8;
+        lds_read_tr8(base + slot_a * 32, alo[f], ahi[f]);
+        lds_read_tr8(base + PART + slot_b * 32, blo[f], bhi[f]);
+      }
+      // all of them have landed; tied to the registers so that no MFMA moves above the wait
+      static_assert(F == 5, "operand list");
+      asm volatile("s_waitcnt lgkmcnt(0)"
+                   : "+v"(alo[0]), "+v"(ahi[0]), "+v"(alo[1]), "+v"(ahi[1]), "+v"(alo[2]), "+v"(ahi[2]), "+v"(alo[3]), "+v"(ahi[3]),
+                     "+v"(alo[4]), "+v"(ahi[4]), "+v"(blo[0]), "+v"(bhi[0]), "+v"(blo[1]), "+v"(bhi[1]), "+v"(blo[2]), "+v"(bhi[2]),
+                     "+v"(blo[3]), "+v"(bhi[3]), "+v"(blo[4]), "+v"(bhi[4]));
+      bf16x8 fa[F], fb[F];
+#pragma unroll
+      for (int f = 0; f < F; ++f) {
+        fa[f] = join_tr8(alo[f], ahi[f]);
+        fb[f] = join_tr8(blo[f], bhi[f]);
       }
 #pragma unroll
       for (int i = 0; i < F; ++i)
