@@ -133,13 +133,15 @@ __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x
   // The arguments live in constant memory, and a compiler short of scalar registers re-reads them at every
   // use: one scalar load and a full wait per pointer test, twenty times over.  Read what the row loop needs
   // once, into values the compiler cannot trace back to memory.
-  const float* addend = a.addend;
-  const bf16_t* addmask = a.addmask;
-  float* out_f32 = a.out_f32;
-  bf16_t* out_b16 = a.out_b16;
+  typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+  typedef const f32x4 __attribute__((address_space(1))) * gcf4;
+  typedef f32x4 __attribute__((address_space(1))) * gf4;
+  typedef const u32x2 __attribute__((address_space(1))) * gcu2;
+  typedef u32x2 __attribute__((address_space(1))) * gu2;
+  uint64_t p_addend = (uint64_t)a.addend, p_mask = (uint64_t)a.addmask, p_f32 = (uint64_t)a.out_f32, p_b16 = (uint64_t)a.out_b16;
   int Co = a.Co;
   int want_stats = a.stats != nullptr;
-  asm volatile("" : "+v"(addend), "+v"(addmask), "+v"(out_f32), "+v"(out_b16), "+v"(Co), "+v"(want_stats));
+  asm volatile("" : "+v"(p_addend), "+v"(p_mask), "+v"(p_f32), "+v"(p_b16), "+v"(Co), "+v"(want_stats));
   {
     const int p = lane & 31, half = lane >> 5;
 #pragma unroll
@@ -164,34 +166,60 @@ __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x
   for (int k = 0; k < PERIOD; ++k)
 #pragma unroll
     for (int e = 0; e < 4; ++e) s1[k][e] = s2[k][e] = 0.f;
+  // Rows leave in groups of G iterations: first every load of the group (LDS tile, addend, mask) from addresses
+  // that are safe whether or not the element exists, then the arithmetic and the stores.  Written as one
+  // conditional body per iteration the loads would each sit behind a branch and pay their latency one by one.
+  constexpr int G = ITERS % 10 == 0 ? 10 : 8;
+  static_assert(ITERS % G == 0 && G % PERIOD == 0, "whole groups");
 #pragma unroll
-  for (int it = 0; it < ITERS; ++it) {
-    const int q = it * 64 + lane;
-    const int p = q / UNITS, un = q % UNITS;
-    const int pix = *reinterpret_cast<const int*>(lds + 32 * PITCH + 4 * p);
-    const int c = c_tile + un * 4;
-    if (pix < 0 || c >= Co) continue;
-    f32x4 v = *reinterpret_cast<const f32x4*>(lds + p * PITCH + un * 16);
-    const size_t o = (size_t)pix * Co + c;
-    if (addend) {
-      float4 ad = *reinterpret_cast<const float4*>(addend + o);
-      if (addmask) {
-        const uint2 mk = *reinterpret_cast<const uint2*>(addmask + o);
-        if (!(bf16_lo(mk.x) > 0.f)) ad.x = 0.f;
-        if (!(bf16_hi(mk.x) > 0.f)) ad.y = 0.f;
-        if (!(bf16_lo(mk.y) > 0.f)) ad.z = 0.f;
-        if (!(bf16_hi(mk.y) > 0.f)) ad.w = 0.f;
-      }
-      v[0] += ad.x; v[1] += ad.y; v[2] += ad.z; v[3] += ad.w;
+  for (int it0 = 0; it0 < ITERS; it0 += G) {
+    bool ok[G];
+    size_t o[G];
+    f32x4 v[G];
+    f32x4 ad[G];
+    u32x2 mk[G];
+#pragma unroll
+    for (int k = 0; k < G; ++k) {
+      const int q = (it0 + k) * 64 + lane;
+      const int p = q / UNITS, un = q % UNITS;
+      const int pix = *reinterpret_cast<const int*>(lds + 32 * PITCH + 4 * p);
+      const int c = c_tile + un * 4;
+      ok[k] = pix >= 0 && c < Co;
+      o[k] = ok[k] ? (size_t)pix * Co + c : 0;
+      v[k] = *reinterpret_cast<const f32x4*>(lds + p * PITCH + un * 16);
     }
-    if (out_f32) *reinterpret_cast<float4*>(out_f32 + o) = make_float4(v[0], v[1], v[2], v[3]);
-    const uint2 packed = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
-    if (out_b16) *reinterpret_cast<uint2*>(out_b16 + o) = packed;
-    if (want_stats) {
-      const float r0 = bf16_lo(packed.x), r1 = bf16_hi(packed.x), r2 = bf16_lo(packed.y), r3 = bf16_hi(packed.y);
-      const int k = it % PERIOD;
-      s1[k][0] += r0; s1[k][1] += r1; s1[k][2] += r2; s1[k][3] += r3;
-      s2[k][0] += r0 * r0; s2[k][1] += r1 * r1; s2[k][2] += r2 * r2; s2[k][3] += r3 * r3;
+    if (p_addend) {
+#pragma unroll
+      for (int k = 0; k < G; ++k) ad[k] = *(gcf4)(p_addend + 4 * o[k]);
+      if (p_mask) {
+#pragma unroll
+        for (int k = 0; k < G; ++k) mk[k] = *(gcu2)(p_mask + 2 * o[k]);
+#pragma unroll
+        for (int k = 0; k < G; ++k) {
+          if (!(bf16_lo(mk[k][0]) > 0.f)) ad[k][0] = 0.f;
+          if (!(bf16_hi(mk[k][0]) > 0.f)) ad[k][1] = 0.f;
+          if (!(bf16_lo(mk[k][1]) > 0.f)) ad[k][2] = 0.f;
+          if (!(bf16_hi(mk[k][1]) > 0.f)) ad[k][3] = 0.f;
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < G; ++k) {
+        v[k] += ad[k];
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < G; ++k) {
+      const u32x2 packed = {pack_bf16x2(v[k][0], v[k][1]), pack_bf16x2(v[k][2], v[k][3])};
+      if (ok[k]) {
+        if (p_f32) *(gf4)(p_f32 + 4 * o[k]) = v[k];
+        if (p_b16) *(gu2)(p_b16 + 2 * o[k]) = packed;
+        if (want_stats) {
+          const float r0 = bf16_lo(packed[0]), r1 = bf16_hi(packed[0]), r2 = bf16_lo(packed[1]), r3 = bf16_hi(packed[1]);
+          const int kk = (it0 + k) % PERIOD;
+          s1[kk][0] += r0; s1[kk][1] += r1; s1[kk][2] += r2; s1[kk][3] += r3;
+          s2[kk][0] += r0 * r0; s2[kk][1] += r1 * r1; s2[kk][2] += r2 * r2; s2[kk][3] += r3 * r3;
+        }
+      }
     }
   }
   if (a.stats) {
