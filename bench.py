@@ -22,9 +22,12 @@ if ROOT not in sys.path:
 PEAK_MFMA_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 
-# algorithmic HBM traffic measured with rocprofv3 counters for the dominant kernel, per launch (bytes);
-# filled in from the committed summaries under profiles/ (None until measured)
-TRAFFIC_BYTES = {}
+# HBM-side traffic measured with rocprofv3 counters for the dominant kernel, per launch (bytes);
+# from the committed summaries under profiles/ (None where not measured)
+TRAFFIC_BYTES = {
+    # profiles/hbm_traffic_conv_kernels_cfg4.md: FETCH_SIZE + WRITE_SIZE, scaled by the 1 GiB copy calibration
+    (4, "conv_patch_kernel<160, 160, 5> 640>640 k3 s1 @8x8"): 93.0e6,
+}
 
 
 def parse_args():
@@ -34,6 +37,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..5 (default 4: WRN-28-10 top module)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="first run 3 plain device copies of 1 GiB (float32): the known traffic a profiler's HBM counters "
+                         "are scaled by")
     ap.add_argument("--cpu-sample-batch", type=int, default=0, help="batch of the oracle sample (0 = pick by config)")
     return ap.parse_args()
 
@@ -43,7 +49,7 @@ def cpu_baseline(idx: int, sample_batch: int):
     import numpy as np
     import fdg_workloads as W
     from oracle import fdg_oracle
-    n = sample_batch or {1: 16, 2: 16, 3: 32, 4: 8, 5: 8}[idx]
+    n = sample_batch or {1: 128, 2: 128, 3: 128, 4: 64, 5: 32}[idx]   # about 10-30 s of oracle time
     spec = W.config(idx, n=n)
     spec.delay = 0
     m = fdg_oracle.OracleModule(spec, np.float32, storage="fp32")
@@ -72,6 +78,13 @@ def main():
     spec = W.config(args.config)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     mod = FdgModule(spec, dev)
     mod.set_params(W.make_params(spec))
 
@@ -111,10 +124,23 @@ def main():
     mod.profile_enable(True)
     for i in range(args.steps):
         step(args.warmup + args.steps + i)
-    prof = mod.profile_read()
+    entries = mod.profile_read()
     mod.profile_enable(False)
-    total_ms = sum(p["total_ms"] for p in prof.values())
-    name, dom = max(prof.items(), key=lambda kv: kv[1]["total_ms"])
+    total_ms = sum(e["total_ms"] for e in entries)
+
+    def merged(key):
+        out = {}
+        for e in entries:
+            k = key(e)
+            acc = out.setdefault(k, dict(calls=0, total_ms=0.0, flops=0.0, bytes=0.0))
+            for f in ("calls", "total_ms", "flops", "bytes"):
+                acc[f] += e[f]
+        return out
+
+    prof = merged(lambda e: e["name"])                       # per kernel class
+    kernels = merged(lambda e: e["kernel"] or e["name"])     # per kernel and layer shape (forward and data
+    #                                                          gradient of a stride-1 3x3 layer run the same kernel)
+    name, dom = max(kernels.items(), key=lambda kv: kv[1]["total_ms"])
     avg_ms = dom["total_ms"] / dom["calls"]
     if dom["flops"] > 0:
         achieved = dom["flops"] / dom["calls"] / (avg_ms * 1e-3) / 1e12
@@ -126,11 +152,17 @@ def main():
                     "frac": achieved / PEAK_HBM_GBS}
     roofline.update({"avg_launch_ms": avg_ms, "calls_per_step": dom["calls"] / args.steps,
                      "share_of_step": dom["total_ms"] / total_ms,
+                     "algorithmic_flops_per_launch": dom["flops"] / dom["calls"],
+                     "algorithmic_bytes_per_launch": dom["bytes"] / dom["calls"],
                      "traffic": TRAFFIC_BYTES.get((args.config, name))})
     classes = {k: {"ms_per_step": v["total_ms"] / args.steps, "calls_per_step": v["calls"] / args.steps,
                    "TFLOP/s": (v["flops"] / (v["total_ms"] * 1e-3) / 1e12) if v["flops"] else None,
                    "GB/s": v["bytes"] / (v["total_ms"] * 1e-3) / 1e9}
                for k, v in sorted(prof.items(), key=lambda kv: -kv[1]["total_ms"])}
+    per_kernel = {k: {"ms_per_step": v["total_ms"] / args.steps, "calls_per_step": v["calls"] / args.steps,
+                      "avg_us": 1e3 * v["total_ms"] / v["calls"],
+                      "TFLOP/s": (v["flops"] / (v["total_ms"] * 1e-3) / 1e12) if v["flops"] else None}
+                  for k, v in sorted(kernels.items(), key=lambda kv: -kv[1]["total_ms"]) if v["flops"]}
     mod.close()
 
     out = {
@@ -143,6 +175,7 @@ def main():
         "step_tflops": W.conv_flops(spec) / (ms_per_step * 1e-3) / 1e12,
         "roofline": roofline,
         "kernel_classes": classes,
+        "conv_kernels": per_kernel,
         "paper_context": "FDG K=2 WRN-28-10: 354.56 images/s on 2x 1080Ti, BP 188.16 on 1x (Table VII); other hardware, whole system",
     }
     if not args.no_cpu_baseline:

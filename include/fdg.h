@@ -160,16 +160,20 @@ fdg_status fdg_output_shape(const fdg_module* m, int32_t out[4]);
 fdg_status fdg_queue_state(const fdg_module* m, int32_t* outstanding, int64_t* oldest_seq,
                            int64_t* newest_seq);
 
-/* Per-kernel-class timing, for measurement only.  While enabled, every launch group of a call is
- * bracketed by two HIP events on the call's stream (this costs a few microseconds per launch, so
- * throughput is measured with profiling off).  fdg_profile_enable synchronises the module's stream and
- * clears the records.  fdg_profile_read synchronises, then sums the records per class into at most
- * `capacity` entries of host memory and stores the number of classes seen in *count:
+/* Per-kernel timing, for measurement only.  While enabled, every launch group of a call is bracketed by
+ * two HIP events on the call's stream (this costs a few microseconds per launch, so throughput is
+ * measured with profiling off).  fdg_profile_enable synchronises the module's stream and clears the
+ * records.  fdg_profile_read synchronises, then sums the records into at most `capacity` entries of host
+ * memory, one per kernel class and -- for convolutions -- per kernel and layer shape, and stores the number
+ * of entries that exist in *count (call with capacity 0 to size the array):
+ *   name     = class ("conv_fwd", "conv_dgrad", "conv_wgrad", "bn_apply", ...),
+ *   kernel   = convolutions: "<kernel as a profiler names it> <ci>><co> k<ksize> s<stride> @<ho>x<wo>", else "",
  *   calls    = launch groups (a stride-2 data gradient is one call of four kernels),
  *   total_ms = summed event time,  flops = algorithmic multiply-add flops (2 per MAC; convolutions only),
  *   bytes    = algorithmic HBM bytes (every operand read once, every result written once).          */
 typedef struct {
   char name[32];
+  char kernel[80];
   int64_t calls;
   double total_ms;
   double flops;

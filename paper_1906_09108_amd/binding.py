@@ -29,7 +29,7 @@ class fdg_layer_desc(ctypes.Structure):
 
 
 class fdg_profile_entry(ctypes.Structure):
-    _fields_ = [("name", ctypes.c_char * 32), ("calls", ctypes.c_int64), ("total_ms", ctypes.c_double),
+    _fields_ = [("name", ctypes.c_char * 32), ("kernel", ctypes.c_char * 80), ("calls", ctypes.c_int64), ("total_ms", ctypes.c_double),
                 ("flops", ctypes.c_double), ("bytes", ctypes.c_double)]
 
 
@@ -235,16 +235,21 @@ class FdgModule:
         if st != FDG_OK:
             raise FdgError(st, "fdg_profile_enable")
 
-    def profile_read(self) -> dict:
-        """{class name: dict(calls, total_ms, flops, bytes)} summed over the records since the enable."""
-        arr = (fdg_profile_entry * 16)()
+    def profile_read(self) -> list:
+        """[dict(name, kernel, calls, total_ms, flops, bytes)]: one entry per kernel class and, for
+        convolutions, per kernel and layer shape, summed over the records since the enable."""
         n = ctypes.c_int32()
-        st = load().fdg_profile_read(self.handle, arr, 16, ctypes.byref(n))
+        st = load().fdg_profile_read(self.handle, None, 0, ctypes.byref(n))
         if st != FDG_OK:
             raise FdgError(st, "fdg_profile_read")
-        return {arr[i].name.decode(): dict(calls=int(arr[i].calls), total_ms=float(arr[i].total_ms),
-                                           flops=float(arr[i].flops), bytes=float(arr[i].bytes))
-                for i in range(min(n.value, 16))}
+        cap = max(int(n.value), 1)
+        arr = (fdg_profile_entry * cap)()
+        st = load().fdg_profile_read(self.handle, arr, cap, ctypes.byref(n))
+        if st != FDG_OK:
+            raise FdgError(st, "fdg_profile_read")
+        return [dict(name=arr[i].name.decode(), kernel=arr[i].kernel.decode(), calls=int(arr[i].calls),
+                     total_ms=float(arr[i].total_ms), flops=float(arr[i].flops), bytes=float(arr[i].bytes))
+                for i in range(min(n.value, cap))]
 
     def queue_state(self) -> Tuple[int, int, int]:
         o, a, b = ctypes.c_int32(), ctypes.c_int64(), ctypes.c_int64()

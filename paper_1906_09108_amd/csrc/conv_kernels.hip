@@ -13,9 +13,14 @@
 // column (l & 15) of B, each with the 8 consecutive k values 8*(l >> 4) .. +7; lane l receives
 // D[4*(l >> 4) + v][l & 15] in accumulator component v.
 #include "conv_common.h"
+#include <stdio.h>
 #include <stdlib.h>
 
 namespace fdg {
+
+static thread_local const char* g_last_kernel = "";
+void note_kernel(const char* name) { g_last_kernel = name; }
+const char* last_kernel() { return g_last_kernel; }
 
 // ------------------------------------------------------------------------------------------------
 // gather-form convolution
@@ -140,6 +145,9 @@ template <int BM, int BN, int WAVES_M, int WAVES_N>
 static hipError_t run_gather(const GatherConvArgs& a, hipStream_t s) {
   const int Mtot = a.N * a.OH * a.OW;
   dim3 grid((Mtot + BM - 1) / BM, (a.Co + BN - 1) / BN, 1);
+  static char name[64];
+  if (!name[0]) snprintf(name, sizeof(name), "conv_gather_kernel<%d, %d, %d, %d>", BM, BN, WAVES_M, WAVES_N);
+  note_kernel(name);
   hipLaunchKernelGGL((conv_gather_kernel<BM, BN, WAVES_M, WAVES_N>), grid, dim3(256), 0, s, a);
   return hipGetLastError();
 }
@@ -321,6 +329,9 @@ static hipError_t run_wgrad(const WgradArgs& a, hipStream_t s) {
   L.ci_tiles = ci_tiles;
   splits = (total_chunks + L.chunks_per_split - 1) / L.chunks_per_split;
   dim3 grid(co_tiles, ci_tiles * a.ntaps, splits);
+  static char name[64];
+  if (!name[0]) snprintf(name, sizeof(name), "conv_wgrad_kernel<%d, %d, %d, %d, %d>", BM, BN, WM, WN, WK);
+  note_kernel(name);
   hipLaunchKernelGGL((conv_wgrad_kernel<BM, BN, WM, WN, WK>), grid, dim3(256), 0, s, a, L);
   return hipGetLastError();
 }

@@ -13,6 +13,7 @@
 //   * workgroups are numbered so that the eight XCDs (workgroup id mod 8) each own a contiguous range of
 //     pixel tiles with all of their channel tiles, keeping operand reuse inside one L2.
 #include "conv_common.h"
+#include <stdio.h>
 #include <stdlib.h>
 #include <type_traits>
 #include <utility>
@@ -431,6 +432,9 @@ static hipError_t run_patch(const GatherConvArgs& a, hipStream_t s) {
   }
   const int Mtot = a.N * a.OH * a.OW;
   const int m_tiles = (Mtot + 127) / 128, n_tiles = (a.Co + BN - 1) / BN;
+  static char name[64];
+  if (!name[0]) snprintf(name, sizeof(name), "conv_patch_kernel<%d, %d, %d>", BN, PR, WS);
+  note_kernel(name);
   hipLaunchKernelGGL((conv_patch_kernel<BN, PR, WS>), dim3(m_tiles * n_tiles), dim3(256), lds, s, a, m_tiles, n_tiles);
   return hipGetLastError();
 }
@@ -459,6 +463,9 @@ static hipError_t run_wide(const GatherConvArgs& a, hipStream_t s) {
   }
   const int Mtot = a.N * a.OH * a.OW;
   const int m_tiles = (Mtot + 127) / 128, n_tiles = (a.Co + BN - 1) / BN;
+  static char name[64];
+  if (!name[0]) snprintf(name, sizeof(name), "conv_gather_dma_kernel<%d, %d>", BN, STAGES);
+  note_kernel(name);
   hipLaunchKernelGGL((conv_gather_dma_kernel<BN, STAGES>), dim3(m_tiles * n_tiles), dim3(256), lds, s, a, m_tiles, n_tiles);
   return hipGetLastError();
 }
@@ -998,6 +1005,7 @@ hipError_t launch_conv_wgrad128(const WgradArgs& a, hipStream_t s) {
   L.period = a.OH / g;
   L.a_step = (long long)64 * a.Co * 2;
   L.b_step = (long long)d_oh_full * a.stride * a.Wi * a.Cx * 2;
+  note_kernel("conv_wgrad128_kernel<5>");
   hipLaunchKernelGGL((conv_wgrad128_kernel<STAGES>), dim3(tiles * L.splits), dim3(256), lds, s, a, L);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || !L.partial) return e;
@@ -1058,6 +1066,7 @@ hipError_t launch_conv_wgrad_wide(const WgradArgs& a, hipStream_t s) {
     hipError_t e = launch_fill_f32(a.dw, elems, 0.f, s);
     if (e != hipSuccess) return e;
   }
+  note_kernel("conv_wgrad_dma_kernel<3>");
   hipLaunchKernelGGL((conv_wgrad_dma_kernel<STAGES>), dim3(tiles * L.splits), dim3(256), lds, s, a, L);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || !use_partial) return e;

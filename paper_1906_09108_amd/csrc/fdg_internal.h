@@ -157,6 +157,11 @@ hipError_t launch_emit_weights(const float* params, bf16_t* warena, const Weight
                                int total_blocks, hipStream_t s);
 
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);  // bytes % 16 == 0
+
+// Name of the convolution kernel the calling thread launched last (as a profiler prints it), for the
+// per-kernel timing records of the module; a literal with static lifetime.
+void note_kernel(const char* name);
+const char* last_kernel();
 hipError_t launch_fill_f32(float* p, size_t count, float v, hipStream_t s);
 
 }  // namespace fdg

@@ -9,6 +9,7 @@
 
 #include "../../include/fdg.h"
 #include "fdg_internal.h"
+#include <string.h>
 
 using namespace fdg;
 
@@ -276,7 +277,7 @@ enum ProfClass { PC_CONV_FWD = 0, PC_CONV_DGRAD, PC_CONV_WGRAD, PC_BN_STATS, PC_
                  PC_WEIGHT_SNAPSHOT, PC_LAYOUT, PC_HEAD, PC_FILL, PC_COUNT };
 static const char* const kProfNames[PC_COUNT] = {"conv_fwd", "conv_dgrad", "conv_wgrad", "bn_stats", "bn_apply", "bn_bwd",
                                                  "sgd", "weight_snapshot", "layout", "head", "fill"};
-struct ProfRecord { int cls; double flops, bytes; hipEvent_t e0, e1; };
+struct ProfRecord { int cls; double flops, bytes; hipEvent_t e0, e1; char kernel[80]; };
 struct Profiler {
   bool on = false;
   bool overflow = false;
@@ -351,6 +352,13 @@ struct ProfScope {
   Profiler* pr = nullptr;
   hipStream_t s;
   hipEvent_t e1 = nullptr;
+  size_t rec = 0;
+  // convolutions: which kernel ran, on which layer shape (call after the launch)
+  void label(const ConvShape& c) {
+    if (!pr) return;
+    snprintf(pr->recs[rec].kernel, sizeof(pr->recs[rec].kernel), "%s %d>%d k%d s%d @%dx%d", last_kernel(), c.Ci, c.Co,
+             c.T == 9 ? 3 : 1, c.stride, c.Ho(), c.Wo());
+  }
   ProfScope(const fdg_module* m, int cls, double flops, double bytes, hipStream_t stream) : s(stream) {
     Profiler& p = m->prof;
     if (!p.on) return;
@@ -359,7 +367,8 @@ struct ProfScope {
     e1 = p.take();
     if (!e0 || !e1) { e1 = nullptr; return; }
     pr = &p;
-    p.recs.push_back(ProfRecord{cls, flops, bytes, e0, e1});
+    p.recs.push_back(ProfRecord{cls, flops, bytes, e0, e1, {0}});
+    rec = p.recs.size() - 1;
     (void)hipEventRecord(e0, s);
   }
   ~ProfScope() { if (pr && e1) (void)hipEventRecord(e1, s); }
@@ -375,20 +384,26 @@ hipError_t mconv_forward(const fdg_module* m, const ConvInfo& c, const bf16_t* x
   const double bytes = 2 * conv_in_elems(c.sh) + 2 * conv_w_elems(c.sh) +
                        conv_out_elems(c.sh) * ((addend ? 4 : 0) + (out_f32 ? 4 : 0) + (out_b16 ? 2 : 0));
   ProfScope ps(m, PC_CONV_FWD, conv_flops(c.sh), bytes, s);
-  return conv_forward(c.sh, x, w, addend, out_f32, out_b16, stats, s);
+  const hipError_t e = conv_forward(c.sh, x, w, addend, out_f32, out_b16, stats, s);
+  ps.label(c.sh);
+  return e;
 }
 hipError_t mconv_dgrad(const fdg_module* m, const ConvInfo& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                        const bf16_t* addmask, float* out_f32, bf16_t* out_b16, hipStream_t s) {
   const double bytes = 2 * conv_out_elems(c.sh) + 2 * conv_w_elems(c.sh) +
                        conv_in_elems(c.sh) * ((addend ? 4 : 0) + (addmask ? 2 : 0) + (out_f32 ? 4 : 0) + (out_b16 ? 2 : 0));
   ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c.sh), bytes, s);
-  return conv_dgrad(c.sh, dy, wt, addend, addmask, out_f32, out_b16, s);
+  const hipError_t e = conv_dgrad(c.sh, dy, wt, addend, addmask, out_f32, out_b16, s);
+  ps.label(c.sh);
+  return e;
 }
 hipError_t mconv_wgrad(const fdg_module* m, const ConvInfo& c, const bf16_t* x, const bf16_t* dy, hipStream_t s) {
   const double bytes = 2 * conv_in_elems(c.sh) + 2 * conv_out_elems(c.sh) + 4.0 * c.sh.Co * c.sh.T * c.sh.Ci;
   ProfScope ps(m, PC_CONV_WGRAD, conv_flops(c.sh), bytes, s);
-  return conv_wgrad(c.sh, x, dy, m->grads() + c.p_off, reinterpret_cast<float*>(m->ws + m->p.o_wscratch),
-                    m->p.wscratch_bytes, /*overwrite=*/true, s);
+  const hipError_t e = conv_wgrad(c.sh, x, dy, m->grads() + c.p_off, reinterpret_cast<float*>(m->ws + m->p.o_wscratch),
+                                  m->p.wscratch_bytes, /*overwrite=*/true, s);
+  ps.label(c.sh);
+  return e;
 }
 
 hipError_t bn_stats(const SlotView& v, const BnInfo& b, const bf16_t* x, hipStream_t s) {
@@ -798,23 +813,27 @@ fdg_status fdg_profile_enable(fdg_module* m, int enable) {
 fdg_status fdg_profile_read(fdg_module* m, fdg_profile_entry* out, int32_t capacity, int32_t* count) {
   if (!m || !count || (capacity > 0 && !out)) return FDG_ERR_INVALID_ARG;
   FDG_TRY(hipStreamSynchronize(m->last_stream));
-  fdg_profile_entry acc[PC_COUNT];
-  for (int i = 0; i < PC_COUNT; ++i) {
-    acc[i] = fdg_profile_entry{};
-    snprintf(acc[i].name, sizeof(acc[i].name), "%s", kProfNames[i]);
-  }
+  // one entry per (class, kernel and layer shape)
+  std::vector<fdg_profile_entry> acc;
   for (const ProfRecord& r : m->prof.recs) {
     float ms = 0.f;
     FDG_TRY(hipEventElapsedTime(&ms, r.e0, r.e1));
-    acc[r.cls].calls += 1;
-    acc[r.cls].total_ms += ms;
-    acc[r.cls].flops += r.flops;
-    acc[r.cls].bytes += r.bytes;
+    size_t i = 0;
+    for (; i < acc.size(); ++i)
+      if (strcmp(acc[i].name, kProfNames[r.cls]) == 0 && strcmp(acc[i].kernel, r.kernel) == 0) break;
+    if (i == acc.size()) {
+      acc.push_back(fdg_profile_entry{});
+      snprintf(acc[i].name, sizeof(acc[i].name), "%s", kProfNames[r.cls]);
+      snprintf(acc[i].kernel, sizeof(acc[i].kernel), "%s", r.kernel);
+    }
+    acc[i].calls += 1;
+    acc[i].total_ms += ms;
+    acc[i].flops += r.flops;
+    acc[i].bytes += r.bytes;
   }
   int n = 0;
-  for (int i = 0; i < PC_COUNT; ++i) {
-    if (acc[i].calls == 0) continue;
-    if (n < capacity) out[n] = acc[i];
+  for (const fdg_profile_entry& e : acc) {
+    if (n < capacity) out[n] = e;
     ++n;
   }
   *count = n;
