@@ -111,18 +111,6 @@ hipError_t launch_bn_stats(const bf16_t* x, float* sums, int M, int C, hipStream
 }
 
 // ---- BN apply: y = relu?( gamma*xhat + beta [+ res] [+ gamma2*xhat2 + beta2] ) ------------------------
-// scale/shift per channel are derived once per block from the accumulated sums.
-__device__ __forceinline__ void bn_coeffs(const float* sums, const float* gamma, const float* beta, int C, float invM,
-                                          float eps, float* sc, float* sh) {
-  for (int c = threadIdx.x; c < C; c += blockDim.x) {
-    const float mean = sums[c] * invM;
-    const float var = fmaxf(sums[C + c] * invM - mean * mean, 0.f);
-    const float is = rsqrtf(var + eps);
-    const float g = gamma[c] * is;
-    sc[c] = g;
-    sh[c] = beta[c] - mean * g;
-  }
-}
 __device__ __forceinline__ void bn_running(const float* sums, float* run_mean, float* run_var, int C, int M, float mom) {
   const float invM = 1.f / (float)M;
   const float unbias = M > 1 ? (float)M / (float)(M - 1) : 1.f;
@@ -134,26 +122,70 @@ __device__ __forceinline__ void bn_running(const float* sums, float* run_mean, f
   }
 }
 
-__global__ __launch_bounds__(kThreads) void bn_apply_kernel(BnApplyArgs a) {
-  extern __shared__ float smem[];  // sc[C], sh[C], sc2[C], sh2[C]
-  const int C = a.C, CG = C >> 3;
-  float *sc = smem, *sh = smem + C, *sc2 = smem + 2 * C, *sh2 = smem + 3 * C;
-  const float invM = 1.f / (float)a.M;
-  bn_coeffs(a.sums, a.gamma, a.beta, C, invM, a.eps, sc, sh);
-  if (a.x2) bn_coeffs(a.sums2, a.gamma2, a.beta2, C, invM, a.eps, sc2, sh2);
-  if (blockIdx.x == 0) {
+// Elementwise kernels over [M, C] with per-channel constants: a thread keeps ONE group of 8 channels for all
+// of its rows, so the constants are computed once per thread and stay in registers (no LDS, no per-element
+// lookups), and a wavefront reads whole 128- or 256-byte row segments.
+struct ApplyShape {
+  int CGB, RL, rows_per_block;
+  dim3 grid;
+};
+static ApplyShape apply_shape(int M, int C) {
+  ApplyShape r;
+  const int CG = C / 8;
+  r.CGB = CG >= 16 ? 16 : (CG >= 8 ? 8 : (CG >= 4 ? 4 : (CG >= 2 ? 2 : 1)));
+  r.RL = kThreads / r.CGB;
+  const int cblocks = (CG + r.CGB - 1) / r.CGB;
+  int rblocks = (2048 + cblocks - 1) / cblocks;
+  const int max_rblocks = (M + r.RL * 4 - 1) / (r.RL * 4);      // at least four rows per thread
+  if (rblocks > max_rblocks) rblocks = max_rblocks;
+  if (rblocks < 1) rblocks = 1;
+  int rpb = (M + rblocks - 1) / rblocks;
+  rpb = (rpb + r.RL - 1) / r.RL * r.RL;
+  r.rows_per_block = rpb;
+  r.grid = dim3(cblocks, (M + rpb - 1) / rpb, 1);
+  return r;
+}
+
+// scale / shift of 8 channels from the accumulated sums
+__device__ __forceinline__ void bn_coeffs8(const float* sums, const float* gamma, const float* beta, int C, int c0, float invM,
+                                           float eps, float (&sc)[8], float (&sh)[8]) {
+  float s1[8], s2[8], g[8], b[8];
+  load8_f32(sums + c0, s1);
+  load8_f32(sums + C + c0, s2);
+  load8_f32(gamma + c0, g);
+  load8_f32(beta + c0, b);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const float mean = s1[i] * invM;
+    const float var = fmaxf(s2[i] * invM - mean * mean, 0.f);
+    const float gi = g[i] * rsqrtf(var + eps);
+    sc[i] = gi;
+    sh[i] = b[i] - mean * gi;
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void bn_apply_kernel(BnApplyArgs a, int CGB, int rows_per_block) {
+  const int C = a.C;
+  if (blockIdx.x == 0 && blockIdx.y == 0) {
     if (a.run_mean) bn_running(a.sums, a.run_mean, a.run_var, C, a.M, a.momentum);
     if (a.x2 && a.run_mean2) bn_running(a.sums2, a.run_mean2, a.run_var2, C, a.M, a.momentum);
   }
-  __syncthreads();
-  const size_t units = (size_t)a.M * CG;
-  for (size_t uidx = (size_t)blockIdx.x * kThreads + threadIdx.x; uidx < units; uidx += (size_t)gridDim.x * kThreads) {
-    const int cg = (int)(uidx % CG);
-    const size_t o = uidx * 8;
+  const int RL = kThreads / CGB;
+  const int cg = blockIdx.x * CGB + threadIdx.x % CGB, rl = threadIdx.x / CGB;
+  const int c0 = cg * 8;
+  if (c0 >= C) return;
+  const float invM = 1.f / (float)a.M;
+  float sc[8], sh[8], sc2[8], sh2[8];
+  bn_coeffs8(a.sums, a.gamma, a.beta, C, c0, invM, a.eps, sc, sh);
+  if (a.x2) bn_coeffs8(a.sums2, a.gamma2, a.beta2, C, c0, invM, a.eps, sc2, sh2);
+  const int row_lo = blockIdx.y * rows_per_block, row_hi = min(a.M, row_lo + rows_per_block);
+#pragma unroll 4
+  for (int row = row_lo + rl; row < row_hi; row += RL) {
+    const size_t o = (size_t)row * C + c0;
     float f[8];
     unpack8(*reinterpret_cast<const uint4*>(a.x + o), f);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) f[i] = f[i] * sc[cg * 8 + i] + sh[cg * 8 + i];
+    for (int i = 0; i < 8; ++i) f[i] = f[i] * sc[i] + sh[i];
     if (a.res_f32) {
       float rr[8];
       load8_f32(a.res_f32 + o, rr);
@@ -164,7 +196,7 @@ __global__ __launch_bounds__(kThreads) void bn_apply_kernel(BnApplyArgs a) {
       float g[8];
       unpack8(*reinterpret_cast<const uint4*>(a.x2 + o), g);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) f[i] += g[i] * sc2[cg * 8 + i] + sh2[cg * 8 + i];
+      for (int i = 0; i < 8; ++i) f[i] += g[i] * sc2[i] + sh2[i];
     }
     if (a.relu) {
 #pragma unroll
@@ -184,8 +216,11 @@ static int stream_grid(size_t units) {
 
 hipError_t launch_bn_apply(const BnApplyArgs& a, hipStream_t s) {
   if (a.C % 8 != 0 || a.C > 2048 || a.M <= 0) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(bn_apply_kernel, dim3(stream_grid((size_t)a.M * (a.C / 8))), dim3(kThreads),
-                     4 * a.C * sizeof(float), s, a);
+  const auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+  if (!al16(a.sums) || !al16(a.gamma) || !al16(a.beta) || (a.x2 && (!al16(a.sums2) || !al16(a.gamma2) || !al16(a.beta2))))
+    return hipErrorInvalidValue;   // per-channel vectors are read 16 bytes at a time
+  const ApplyShape r = apply_shape(a.M, a.C);
+  hipLaunchKernelGGL(bn_apply_kernel, r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block);
   return hipGetLastError();
 }
 
@@ -266,37 +301,47 @@ hipError_t launch_bn_bwd_reduce(const BnBwdArgs& a, hipStream_t s) {
 
 // dx = gamma*invstd*(g - S1/M - xhat*S2/M) [+ addend];  dgamma = S2, dbeta = S1
 template <bool DY_F32>
-__global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(BnBwdArgs a) {
-  extern __shared__ float smem[];  // mean[C], is[C], k1[C] (= S1/M), k2[C] (= S2/M), gi[C] (= gamma*is)
-  const int C = a.C, CG = C >> 3;
-  float *mean = smem, *is = smem + C, *k1 = smem + 2 * C, *k2 = smem + 3 * C, *gi = smem + 4 * C;
+__global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(BnBwdArgs a, int CGB, int rows_per_block) {
+  const int C = a.C;
+  const int RL = kThreads / CGB;
+  const int cg = blockIdx.x * CGB + threadIdx.x % CGB, rl = threadIdx.x / CGB;
+  const int c0 = cg * 8;
+  if (c0 >= C) return;
   const float invM = 1.f / (float)a.M;
-  bn_moments(a.sums, C, invM, a.eps, mean, is);
-  __syncthreads();
-  for (int c = threadIdx.x; c < C; c += blockDim.x) {
-    const float s1 = a.bsums[c], s2 = a.bsums[C + c];
-    k1[c] = s1 * invM;
-    k2[c] = s2 * invM;
-    gi[c] = a.gamma[c] * is[c];
-    if (blockIdx.x == 0) {
-      a.dbeta[c] = s1;
-      a.dgamma[c] = s2;
+  // per channel: xhat = x*is - mean*is;  dx = gi*g - gi*k1 - gi*k2*xhat = gi*g + (pa*x + pb)
+  float gi[8], pa[8], pb[8];
+  {
+    float s1[8], s2[8], gm[8], b1[8], b2[8];
+    load8_f32(a.sums + c0, s1);
+    load8_f32(a.sums + C + c0, s2);
+    load8_f32(a.gamma + c0, gm);
+    load8_f32(a.bsums + c0, b1);
+    load8_f32(a.bsums + C + c0, b2);
+    if (blockIdx.y == 0 && rl == 0) {
+      store8_f32(a.dbeta + c0, b1);
+      store8_f32(a.dgamma + c0, b2);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float mean = s1[i] * invM;
+      const float var = fmaxf(s2[i] * invM - mean * mean, 0.f);
+      const float is = rsqrtf(var + a.eps);
+      gi[i] = gm[i] * is;
+      const float k1 = b1[i] * invM, k2 = b2[i] * invM;
+      pa[i] = -gi[i] * k2 * is;
+      pb[i] = -gi[i] * k1 + gi[i] * k2 * is * mean;
     }
   }
-  __syncthreads();
   if (!a.out_f32 && !a.out_b16) return;
-  const size_t units = (size_t)a.M * CG;
-  for (size_t uidx = (size_t)blockIdx.x * kThreads + threadIdx.x; uidx < units; uidx += (size_t)gridDim.x * kThreads) {
-    const int c0 = (int)(uidx % CG) * 8;
-    const size_t o = uidx * 8;
+  const int row_lo = blockIdx.y * rows_per_block, row_hi = min(a.M, row_lo + rows_per_block);
+#pragma unroll 4
+  for (int row = row_lo + rl; row < row_hi; row += RL) {
+    const size_t o = (size_t)row * C + c0;
     float g[8], xv[8];
     load_masked_dy<DY_F32>(a.dy, a.mask, o, g);
     unpack8(*reinterpret_cast<const uint4*>(a.x + o), xv);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const float xh = (xv[i] - mean[c0 + i]) * is[c0 + i];
-      g[i] = gi[c0 + i] * (g[i] - k1[c0 + i] - xh * k2[c0 + i]);
-    }
+    for (int i = 0; i < 8; ++i) g[i] = gi[i] * g[i] + (pa[i] * xv[i] + pb[i]);
     if (a.addend) {
       float ad[8];
       load8_f32(a.addend + o, ad);
@@ -310,12 +355,14 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(BnBwdArgs a) {
 
 hipError_t launch_bn_bwd_apply(const BnBwdArgs& a, hipStream_t s) {
   if (a.C % 8 != 0 || a.C > 2048 || a.M <= 0 || !a.mask) return hipErrorInvalidValue;
-  const int grid = (a.out_f32 || a.out_b16) ? stream_grid((size_t)a.M * (a.C / 8)) : 1;
-  const size_t sm = 5 * (size_t)a.C * sizeof(float);
+  const auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+  if (!al16(a.sums) || !al16(a.gamma) || !al16(a.bsums) || !al16(a.dgamma) || !al16(a.dbeta)) return hipErrorInvalidValue;
+  ApplyShape r = apply_shape(a.M, a.C);
+  if (!a.out_f32 && !a.out_b16) r.grid.y = 1;   // only dgamma / dbeta
   if (a.dy_is_f32)
-    hipLaunchKernelGGL(bn_bwd_apply_kernel<true>, dim3(grid), dim3(kThreads), sm, s, a);
+    hipLaunchKernelGGL(bn_bwd_apply_kernel<true>, r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block);
   else
-    hipLaunchKernelGGL(bn_bwd_apply_kernel<false>, dim3(grid), dim3(kThreads), sm, s, a);
+    hipLaunchKernelGGL(bn_bwd_apply_kernel<false>, r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block);
   return hipGetLastError();
 }
 
