@@ -170,9 +170,10 @@ __global__ __launch_bounds__(256) void conv_gather_dma_kernel(GatherConvArgs a, 
 // channel block and the weights WS stages deep, looks nine taps (patch) and WS-1 taps (weights) ahead, which
 // covers an L2 miss.  A tap that falls outside the image reads a zero region of LDS instead.
 //
-// Order of the direct-to-LDS loads in every wave: patch(0), w(0..WS-2), then at step i = 9c + t (after the
-// barrier): w(i+WS-1) and, when t == 0, patch(c+1).  Loads complete in order, so "w(i) has landed" is
-// vmcnt <= (WS-2)*JW, plus JX when patch(c+1) was issued after w(i), i.e. for 1 <= t <= WS-1.
+// Order of the direct-to-LDS loads in every wave: patch(0), w(0..WS-2), then per step i = 9c + t one group:
+// w(i+WS-1) and, for t < XG, a share of patch(c+1).  Barrier i+1 (step i+1 visible) is taken after slot 1 of
+// step i; loads complete in order, so "w(i+1) has landed" is vmcnt <= the sizes of the WS-3 groups issued after
+// the one that carried it.
 template <class F, int... I>
 __device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
   (f(std::integral_constant<int, I>{}), ...);
@@ -346,12 +347,45 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
   asm volatile("" ::: "memory");
   static_for<NFRAG>([&](auto idx) { read_one(set0{}, idx, 0, 0, std::integral_constant<int, 0>{}, 0); });
 
+  // Loads are issued thinly: a step's group of loads -- the weights of step i + WS - 1 and, in the first XG steps
+  // of a channel block, a share of the next block's patch -- goes out one load every other slot over the whole
+  // step.  Issued in a burst, the loads fill the address queue, the wave stalls on the next one and the MFMAs
+  // behind it starve, although the step has time for all of them.
+  constexpr int XG = 11 - WS;                       // groups that may carry patch loads (landed by the block's end)
+  constexpr int PER = (JX + XG - 1) / XG;           // patch loads per such group
+  static_assert(3 + 2 * (JW + PER - 1) < 2 * NM, "one load every other slot fits the step");
+  // loads in the group of tap t (t < 0: a tap of the previous block, or the prologue)
+  auto gsize = [](int t, bool last) constexpr {
+    if (t < 0) return JW;
+    const int w = last ? (t + WS - 1 <= 8 ? JW : 0) : JW;
+    const int left = JX - t * PER;
+    const int x = (!last && t < XG && left > 0) ? (left < PER ? left : PER) : 0;
+    return w + x;
+  };
   int slot = 0;   // weight stage of the current step
   auto chunk_body = [&](int c, auto last_tag) {
     constexpr bool LAST = decltype(last_tag)::value;
     static_for<9>([&](auto t_tag) {
       constexpr int T = decltype(t_tag)::value;
-      // first half step: MFMAs of set 0, reads of this step's second half into set 1
+      const int nslot = slot == WS - 1 ? 0 : slot + 1;
+      const int islot = slot == 0 ? WS - 1 : slot - 1;
+      constexpr bool MORE = !(LAST && T == 8);            // a next step exists
+      constexpr int TT = T + WS - 1;                      // tap of the step whose weights are issued now
+      constexpr bool ISSUE_W = TT < 9 || !LAST;
+      constexpr int NW = ISSUE_W ? JW : 0;
+      constexpr int NX = gsize(T, LAST) - NW;             // patch loads of this group: pieces T*PER ...
+      const int kbyte = TT < 9 ? tko[TT < 9 ? TT : 0] + c * 128 : tko[TT < 9 ? 0 : TT - 9] + (c + 1) * 128;
+      // load idx of the group goes out after the MFMA of global slot 3 + 2 idx (slots 0 .. 2 NM - 1 over both halves)
+      auto issue_at = [&](auto s_tag) {
+        constexpr int SL = decltype(s_tag)::value;
+        if constexpr (SL >= 3 && (SL - 3) % 2 == 0) {
+          constexpr int IDX = (SL - 3) / 2;
+          if constexpr (IDX < NW) issue_w_one(IDX, islot, kbyte);
+          else if constexpr (IDX - NW < NX) issue_x_one(T * PER + IDX - NW, c + 1);
+        }
+      };
+      // first half step: MFMAs of set 0, reads of this step's second half into set 1.  After slot 1: barrier
+      // T+1 (next step visible; everybody done reading the previous step, whose stage the group overwrites).
       static_for<NM>([&](auto k) {
         constexpr int K = decltype(k)::value;
         // set 1 is filled one fragment per slot from slot 0 on
@@ -359,16 +393,19 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
           before_mma(set0{}, k, std::integral_constant<int, left_after(K) + (K < NFRAG ? K : NFRAG)>{});
         mma_one(set0{}, k);
         if constexpr (K < NFRAG) read_one(set1{}, k, slot, c & 1, t_tag, 1);
+        if constexpr (MORE && K == 1) {
+          constexpr int PENDING = (WS >= 4 ? gsize(T - 1, LAST) : 0) + (WS >= 5 ? gsize(T - 2, LAST) : 0) +
+                                  (WS >= 6 ? gsize(T - 3, LAST) : 0) + (WS >= 7 ? gsize(T - 4, LAST) : 0);
+          static_assert(WS <= 7, "terms above");
+          wait_vmcnt<PENDING>();
+          asm volatile("" ::: "memory");
+          __builtin_amdgcn_s_barrier();
+          asm volatile("" ::: "memory");
+        }
+        if constexpr (MORE) issue_at(std::integral_constant<int, K>{});
         __builtin_amdgcn_sched_barrier(0);
       });
-      // second half step: MFMAs of set 1; barrier, then the next step's first reads and the DMA issue
-      const int nslot = slot == WS - 1 ? 0 : slot + 1;
-      const int islot = slot == 0 ? WS - 1 : slot - 1;
-      constexpr bool MORE = !(LAST && T == 8);            // a next step exists
-      constexpr int TT = T + WS - 1;                      // tap of the step issued now
-      constexpr bool ISSUE_W = TT < 9 || !LAST;
-      constexpr bool ISSUE_X = T == 0 && !LAST;
-      const int kbyte = TT < 9 ? tko[TT < 9 ? TT : 0] + c * 128 : tko[TT < 9 ? 0 : TT - 9] + (c + 1) * 128;
+      // second half step: MFMAs of set 1, the next step's first reads into set 0
       static_for<NM>([&](auto k) {
         constexpr int K = decltype(k)::value;
         // set 0 of the next step is filled one fragment per slot from slot 2 on (when there is a next step)
@@ -376,24 +413,11 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
           before_mma(set1{}, k, std::integral_constant<int, left_after(K) + ((MORE && K > 2) ? (K - 2 < NFRAG ? K - 2 : NFRAG) : 0)>{});
         mma_one(set1{}, k);
         if constexpr (MORE) {
-          if constexpr (K == 1) {
-            constexpr int AHEAD = LAST ? ((7 - T) < (WS - 3) ? (7 - T) : (WS - 3)) : (WS - 3);
-            constexpr int XPEND = (!LAST && T >= 1 && T <= WS - 2) ? JX : 0;
-            wait_vmcnt<AHEAD * JW + XPEND>();
-            asm volatile("" ::: "memory");
-            __builtin_amdgcn_s_barrier();
-            asm volatile("" ::: "memory");
-          }
           if constexpr (K >= 2 && K - 2 < NFRAG) {
             if constexpr (T < 8) read_one(set0{}, std::integral_constant<int, K - 2>{}, nslot, c & 1, std::integral_constant<int, (T + 1) % 9>{}, 0);
             else read_one(set0{}, std::integral_constant<int, K - 2>{}, nslot, (c + 1) & 1, std::integral_constant<int, 0>{}, 0);
           }
-          if constexpr (ISSUE_W && K >= 2 && K - 2 < JW) issue_w_one(K - 2, islot, kbyte);
-          if constexpr (ISSUE_X && K >= 2 + JW) {
-            constexpr int XSLOTS = NM - 2 - JW, PER = (JX + XSLOTS - 1) / XSLOTS;
-#pragma unroll
-            for (int j = (K - 2 - JW) * PER; j < (K - 1 - JW) * PER && j < JX; ++j) issue_x_one(j, c + 1);
-          }
+          issue_at(std::integral_constant<int, NM + K>{});
         }
         __builtin_amdgcn_sched_barrier(0);
       });
