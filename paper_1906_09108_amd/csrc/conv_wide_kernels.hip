@@ -880,14 +880,22 @@ __global__ __launch_bounds__(256) void conv_wgrad128_kernel(WgradArgs a, Wgrad12
   using set1 = std::integral_constant<int, 1>;
   static_for<2 * NF>([&](auto idx) { read_one(set0{}, idx, 0, 0); });
 
-  // One chunk = two half steps of NM (MFMA, piece) slots.  First half: MFMAs of set 0, reads of the second
-  // step into set 1.  Second half: MFMAs of set 1; after slot 1 barrier c+1 (chunk c+1 visible; everybody done
-  // reading chunk c-1), then the first-step reads of chunk c+1 into set 0 and the loads of chunk c+STAGES-1
-  // (into the stage of chunk c-1).  AHEAD = chunks issued beyond c+1 when the barrier is reached.
-  static_assert(2 * NF <= 2 * (NM - 2) && NJ <= 2 * (NM - 2), "slots of a half step");
+  // One chunk = two half steps of NM (MFMA, piece) slots.  First half: MFMAs of set 0, reads of the second step
+  // into set 1; after slot 1 barrier c+1 (chunk c+1 visible; everybody done reading chunk c-1).  Second half:
+  // MFMAs of set 1, first-step reads of chunk c+1 into set 0.  The NJ loads of chunk c+STAGES-1 (into the stage
+  // of chunk c-1) go out one every other slot from the barrier to the end of the chunk: in a burst they fill the
+  // address queue and the wave stalls, MFMAs included.  AHEAD = chunks issued beyond c+1 at the barrier.
+  static_assert(2 * NF <= 2 * (NM - 2) && 2 + 2 * (NJ - 1) < 2 * NM + 1, "slots of a chunk");
   auto step = [&](auto next_tag, auto issue_tag, auto ahead_tag, int c) {
     constexpr bool NEXT = decltype(next_tag)::value, ISSUE = decltype(issue_tag)::value;
     constexpr int AHEAD = decltype(ahead_tag)::value;
+    auto issue_at = [&](auto s_tag) {   // global slot 0 .. 2 NM - 1: load d after slot 2 + 2 d (the last one shares slot 2 NM - 1)
+      constexpr int SL = decltype(s_tag)::value;
+      if constexpr (ISSUE) {
+        if constexpr (SL >= 2 && (SL - 2) % 2 == 0 && (SL - 2) / 2 < NJ) issue_one((SL - 2) / 2, c + STAGES - 1);
+        if constexpr (SL == 2 * NM - 1 && 2 + 2 * (NJ - 1) >= 2 * NM) issue_one(NJ - 1, c + STAGES - 1);
+      }
+    };
     static_for<NM>([&](auto k) {
       constexpr int K = decltype(k)::value;
       // 12 reads per set, two per slot: set 1 is filled in slots 0..5 of this half
@@ -897,6 +905,13 @@ __global__ __launch_bounds__(256) void conv_wgrad128_kernel(WgradArgs a, Wgrad12
         read_one(set1{}, std::integral_constant<int, 2 * K>{}, c, 1);
         read_one(set1{}, std::integral_constant<int, 2 * K + 1>{}, c, 1);
       }
+      if constexpr (NEXT && K == 1) {
+        wait_vmcnt<AHEAD * NJ>();
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+      }
+      issue_at(std::integral_constant<int, K>{});
       __builtin_amdgcn_sched_barrier(0);
     });
     static_for<NM>([&](auto k) {
@@ -907,23 +922,12 @@ __global__ __launch_bounds__(256) void conv_wgrad128_kernel(WgradArgs a, Wgrad12
       before_mma(set1{}, k, std::integral_constant<int, (K <= 4 ? LEFT + NEWER : 15)>{});
       mma_one(set1{}, k);
       if constexpr (NEXT) {
-        if constexpr (K == 1) {
-          wait_vmcnt<AHEAD * NJ>();
-          asm volatile("" ::: "memory");
-          __builtin_amdgcn_s_barrier();
-          asm volatile("" ::: "memory");
-        }
         if constexpr (K >= 2 && 2 * (K - 2) < 2 * NF) {
           read_one(set0{}, std::integral_constant<int, 2 * (K - 2)>{}, c + 1, 0);
           read_one(set0{}, std::integral_constant<int, 2 * (K - 2) + 1>{}, c + 1, 0);
         }
       }
-      if constexpr (ISSUE && K >= 2) {
-        // NJ pieces over the NM - 2 slots after the barrier
-        constexpr int PER = (NJ + NM - 3) / (NM - 2);
-#pragma unroll
-        for (int d = (K - 2) * PER; d < (K - 1) * PER && d < NJ; ++d) issue_one(d, c + STAGES - 1);
-      }
+      issue_at(std::integral_constant<int, NM + K>{});
       __builtin_amdgcn_sched_barrier(0);
     });
     if constexpr (ISSUE) issue_done();
