@@ -1,0 +1,156 @@
+"""The convolution and batch-norm kernels at the benchmark's full sizes (configuration 4, batch 128), in
+the launch configuration bench.py times, checked on sub-problems the oracle computes exactly:
+
+  * forward and data gradient are independent per image, so the oracle runs on a few images of the batch
+    and those images' outputs are compared element by element;
+  * the weight gradient contracts over pixels only, so for a few output and input channels the oracle's
+    weight gradient of the channel-restricted operands IS that block of the full gradient;
+  * batch norm is independent per channel: the oracle runs on a few channels over all rows;
+  * the fused statistics are compared with sums of the tensor the kernel wrote (holds at any size).
+
+Inputs are bf16-representable and given to both sides, so only accumulation order and output rounding
+differ (tolerances as in test_gpu_kernels.py)."""
+import numpy as np
+import pytest
+
+from oracle.fdg_oracle import Kernels
+
+pytestmark = pytest.mark.gpu
+
+F32_TOL = 2e-4
+B16_TOL = 2.0 ** -8
+K32 = Kernels(np.float32)
+
+# the layer shapes of configuration 4 (WRN-28-10 top module): n, h, w, ci, co, ksize, stride
+FULL_CASES = [
+    (128, 8, 8, 640, 640, 3, 1),
+    (128, 16, 16, 320, 320, 3, 1),
+    (128, 16, 16, 320, 640, 3, 2),
+    (128, 16, 16, 320, 640, 1, 2),
+]
+IMAGES = [0, 63, 127]
+
+
+def _t():
+    import torch
+    return torch
+
+
+def rel(got, ref):
+    d = np.abs(ref).max()
+    return float(np.abs(np.asarray(got, np.float64) - ref).max() / (d if d > 0 else 1.0))
+
+
+def _dev_bf16(shape, seed, scale=1.0):
+    """A bf16 device tensor of N(0, scale^2) values and the same values on the host in fp32."""
+    t = _t()
+    g = t.Generator(device="cpu").manual_seed(seed)
+    a = (t.randn(shape, generator=g) * scale).to(t.bfloat16)
+    return a.cuda(), a.to(t.float32).numpy()
+
+
+@pytest.mark.parametrize("case", FULL_CASES)
+def test_conv_forward_and_data_gradient_on_sampled_images(case):
+    from paper_1906_09108_amd import kernels as K
+    t = _t()
+    n, h, w, ci, co, k, s = case
+    print("full-size conv fwd/dgrad", case, flush=True)
+    pad = 1 if k == 3 else 0
+    ho, wo = (h - 1) // s + 1, (w - 1) // s + 1
+    xd, x = _dev_bf16((n, h, w, ci), 1)                               # NHWC
+    wd, wt = _dev_bf16((co, k * k, ci), 2, (2.0 / (ci * k * k)) ** 0.5)  # [co][tap][ci]
+    w_oihw = wt.reshape(co, k, k, ci).transpose(0, 3, 1, 2).copy()
+    y16 = t.zeros((n, ho, wo, co), dtype=t.bfloat16, device="cuda")
+    y32 = t.full((n, ho, wo, co), float("nan"), dtype=t.float32, device="cuda")
+    stats = t.zeros(2 * co, dtype=t.float32, device="cuda")
+    K.fdgk_conv_fwd(xd, wd, None, y32, y16, stats, n, h, w, ci, co, k, s)
+    t.cuda.synchronize()
+    x_sel = x[IMAGES].transpose(0, 3, 1, 2).copy()
+    ref = K32.conv_fwd(x_sel, w_oihw, s, pad).astype(np.float64)       # [3, co, ho, wo]
+    got32 = y32[IMAGES].cpu().numpy().transpose(0, 3, 1, 2)
+    got16 = y16[IMAGES].to(t.float32).cpu().numpy().transpose(0, 3, 1, 2)
+    assert rel(got32, ref) <= F32_TOL
+    assert rel(got16, ref) <= B16_TOL
+    yb = y16.to(t.float64).reshape(-1, co)
+    st = stats.cpu().numpy().astype(np.float64)
+    assert rel(st[:co], yb.sum(0).cpu().numpy()) <= 1e-5
+    assert rel(st[co:], (yb * yb).sum(0).cpu().numpy()) <= 1e-5
+    assert bool(t.isfinite(y32).all())
+
+    # data gradient with the same weights stored [ci][tap][co]
+    dyd, dy = _dev_bf16((n, ho, wo, co), 3)
+    wtd = wd.permute(2, 1, 0).contiguous()
+    dx32 = t.full((n, h, w, ci), float("nan"), dtype=t.float32, device="cuda")
+    dx16 = t.zeros((n, h, w, ci), dtype=t.bfloat16, device="cuda")
+    K.fdgk_conv_dgrad(dyd, wtd, None, None, dx32, dx16, n, h, w, ci, co, k, s)
+    t.cuda.synchronize()
+    dy_sel = dy[IMAGES].transpose(0, 3, 1, 2).copy()
+    dref = K32.conv_bwd_data(dy_sel, w_oihw, (len(IMAGES), ci, h, w), s, pad).astype(np.float64)
+    assert rel(dx32[IMAGES].cpu().numpy().transpose(0, 3, 1, 2), dref) <= F32_TOL
+    assert rel(dx16[IMAGES].to(t.float32).cpu().numpy().transpose(0, 3, 1, 2), dref) <= B16_TOL
+    assert bool(t.isfinite(dx32).all())
+
+
+@pytest.mark.parametrize("case", FULL_CASES)
+def test_conv_weight_gradient_on_sampled_channels(case):
+    from paper_1906_09108_amd import kernels as K
+    t = _t()
+    n, h, w, ci, co, k, s = case
+    print("full-size conv wgrad", case, flush=True)
+    pad = 1 if k == 3 else 0
+    ho, wo = (h - 1) // s + 1, (w - 1) // s + 1
+    xd, x = _dev_bf16((n, h, w, ci), 5)
+    dyd, dy = _dev_bf16((n, ho, wo, co), 6)
+    co_sel = [0, 31, 32, 127, 128, co // 2 + 1, co - 33, co - 1]      # across MFMA blocks, tiles and both ends
+    ci_sel = [0, 15, 16, 63, 64, ci // 2 - 1, ci - 65, ci - 1]
+    x_sel = x[..., ci_sel].transpose(0, 3, 1, 2).copy()
+    dy_sel = dy[..., co_sel].transpose(0, 3, 1, 2).copy()
+    ref = K32.conv_bwd_weight(x_sel, dy_sel, k, s, pad).astype(np.float64)   # [8, 8, k, k]
+    nbytes = K.fdgk_conv_wgrad_scratch_bytes(n, h, w, ci, co, k, s)
+    scratch = t.full((max(nbytes // 4, 4),), float("nan"), dtype=t.float32, device="cuda")
+    dw = t.full((co, k * k, ci), 7.0, dtype=t.float32, device="cuda")
+    K.fdgk_conv_wgrad(xd, dyd, dw, scratch if nbytes else None, n, h, w, ci, co, k, s, overwrite=True)
+    t.cuda.synchronize()
+    assert bool(t.isfinite(dw).all())
+    got = dw.cpu().numpy().reshape(co, k, k, ci)[co_sel][:, :, :, ci_sel].transpose(0, 3, 1, 2)
+    # fp32 accumulation over up to 32768 pixel products of unit-variance operands
+    assert rel(got, ref) <= F32_TOL
+
+
+@pytest.mark.parametrize("m,c", [(128 * 8 * 8, 640), (128 * 16 * 16, 320)])
+def test_batch_norm_on_sampled_channels(m, c):
+    from paper_1906_09108_amd import kernels as K
+    t = _t()
+    print("full-size bn", m, c, flush=True)
+    eps = 1e-5
+    sel = [0, 7, 8, c // 2, c - 9, c - 1]
+    r = np.random.default_rng(m + c)
+    xd, x = _dev_bf16((m, c), 11, 1.5)
+    gamma = (1 + 0.2 * r.standard_normal(c)).astype(np.float32)
+    beta = (0.2 * r.standard_normal(c)).astype(np.float32)
+    gd, bd = t.from_numpy(gamma).cuda(), t.from_numpy(beta).cuda()
+    sums = t.zeros(2 * c, dtype=t.float32, device="cuda")
+    K.fdgk_bn_stats(xd, sums, m, c)
+    y32 = t.empty((m, c), dtype=t.float32, device="cuda")
+    y16 = t.empty((m, c), dtype=t.bfloat16, device="cuda")
+    K.fdgk_bn_apply(xd, sums, gd, bd, None, y32, y16, m, c, eps, 1)
+    t.cuda.synchronize()
+    x4 = x[:, sel].T.reshape(1, len(sel), m, 1).copy()
+    y_ref, mean, var, invstd = K32.bn_fwd(x4, gamma[sel], beta[sel], eps)
+    out_ref = np.maximum(y_ref.reshape(len(sel), m).T.astype(np.float64), 0)
+    assert rel(y32[:, sel].cpu().numpy(), out_ref) <= F32_TOL
+    assert rel(y16[:, sel].to(t.float32).cpu().numpy(), out_ref) <= B16_TOL
+    # backward through the ReLU gate, fp32 incoming gradient
+    dyd = t.randn((m, c), generator=t.Generator(device="cpu").manual_seed(12)).cuda()
+    gate = (y16[:, sel].to(t.float32).cpu().numpy() > 0)
+    g = (dyd[:, sel].cpu().numpy() * gate).astype(np.float32)
+    dx_ref, dgamma_ref, dbeta_ref = K32.bn_bwd(x4, g.T.reshape(1, len(sel), m, 1).copy(), gamma[sel], mean, invstd)
+    scratch = t.zeros(2 * c, dtype=t.float32, device="cuda")
+    dx32 = t.empty((m, c), dtype=t.float32, device="cuda")
+    dg, db = t.empty(c, dtype=t.float32, device="cuda"), t.empty(c, dtype=t.float32, device="cuda")
+    K.fdgk_bn_bwd(dyd, True, y16, xd, sums, gd, scratch, None, dx32, None, dg, db, m, c, eps)
+    t.cuda.synchronize()
+    assert rel(db[sel].cpu().numpy(), dbeta_ref.astype(np.float64)) <= F32_TOL
+    assert rel(dg[sel].cpu().numpy(), dgamma_ref.astype(np.float64)) <= F32_TOL
+    assert rel(dx32[:, sel].cpu().numpy(), dx_ref.reshape(len(sel), m).T.astype(np.float64)) <= F32_TOL
+    assert bool(t.isfinite(dx32).all())
