@@ -87,3 +87,10 @@ def test_configs_reduced_batch(idx, n, steps):
     spec = W.config(idx, n=n)
     print(f"case cfg{idx} n={n}", flush=True)
     _check(spec, steps=steps, strict=False, perturb_bn=False)
+
+
+def test_config4_full_batch():
+    """The bench workload itself (WRN-28-10 top module, batch 128): one iteration next to both oracle runs."""
+    spec = W.config(4)
+    print("case cfg4 full batch", flush=True)
+    _check(spec, steps=1, strict=False, perturb_bn=False)
