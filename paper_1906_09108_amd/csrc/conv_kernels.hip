@@ -393,6 +393,36 @@ hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, co
   }
   // stride 2: input pixels of one parity class (ph, pw) share one set of taps:
   // hi = 2*oh + ph receives tap r only if hi + 1 - r is even, from output row (hi + 1 - r) / 2.
+  {
+    // wide layers: all four classes in one launch, heaviest first (4, 2, 2, 1 taps of a 3x3 filter)
+    GatherConvArgs probe = a;
+    probe.OH = (c.Hi + 1) / 2; probe.OW = (c.Wi + 1) / 2; probe.ntaps = 1; probe.tap[0] = pack_tap(0, 0, 0);
+    if (conv_gather_wide_applies(probe) && c.Hi >= 2 && c.Wi >= 2) {
+      static const int order[4][2] = {{1, 1}, {0, 1}, {1, 0}, {0, 0}};
+      a.nclass = 4;
+      a.out_stride = 2;
+      for (int i = 0; i < 4; ++i) {
+        const int ph = order[i][0], pw = order[i][1];
+        a.cOH[i] = (c.Hi - ph + 1) / 2; a.cOW[i] = (c.Wi - pw + 1) / 2;
+        a.cooh[i] = ph; a.coow[i] = pw;
+        int nt = 0;
+        if (c.T == 9) {
+          for (int r = 0; r < 3; ++r) {
+            if (((ph + 1 - r) & 1) != 0) continue;
+            for (int q = 0; q < 3; ++q) {
+              if (((pw + 1 - q) & 1) != 0) continue;
+              a.ctap[i][nt++] = pack_tap((ph + 1 - r) / 2, (pw + 1 - q) / 2, r * 3 + q);
+            }
+          }
+        } else if (ph == 0 && pw == 0) {
+          a.ctap[i][nt++] = pack_tap(0, 0, 0);
+        }
+        a.cntaps[i] = nt;
+      }
+      a.OH = a.cOH[0]; a.OW = a.cOW[0]; a.ooh = 1; a.oow = 1; a.ntaps = 0;
+      return launch_conv_gather_wide(a, s);
+    }
+  }
   for (int ph = 0; ph < 2; ++ph)
     for (int pw = 0; pw < 2; ++pw) {
       a.OH = (c.Hi - ph + 1) / 2; a.OW = (c.Wi - pw + 1) / 2;

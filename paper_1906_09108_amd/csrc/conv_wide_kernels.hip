@@ -53,12 +53,20 @@ __global__ __launch_bounds__(256) void conv_gather_dma_kernel(GatherConvArgs a, 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: it selects DMA destinations
   const int wave_m = wave & 1, wk = wave >> 1;
-  const int Mtot = a.N * a.OH * a.OW;
 
   // workgroup -> tile, XCD aware: hardware deals workgroup ids round robin over 8 XCDs
-  int t = blockIdx.x;
-  const int total = m_tiles * n_tiles;
-  if ((total & 7) == 0) t = (blockIdx.x & 7) * (total >> 3) + (blockIdx.x >> 3);
+  GatherConvArgs b = a;      // the geometry this workgroup works on
+  int t = blockIdx.x, cls = 0;
+  if (a.nclass > 1) {
+    // classes are ordered by decreasing work, so the plain order lets the dispatcher balance them
+    while (cls + 1 < a.nclass && t >= a.cls_start[cls + 1]) ++cls;
+    t -= a.cls_start[cls];
+    b.OH = a.cOH[cls]; b.OW = a.cOW[cls]; b.ooh = a.cooh[cls]; b.oow = a.coow[cls]; b.ntaps = a.cntaps[cls];
+  } else {
+    const int total = m_tiles * n_tiles;
+    if ((total & 7) == 0) t = (blockIdx.x & 7) * (total >> 3) + (blockIdx.x >> 3);
+  }
+  const int Mtot = b.N * b.OH * b.OW;
   const int m0 = (t / n_tiles) * BM, c0 = (t % n_tiles) * BN;
 
   // ---- per-thread DMA sources: row = 8*(4*j + wave) + lane/8, LDS unit lane%8 holds k-unit u ----
@@ -72,7 +80,7 @@ __global__ __launch_bounds__(256) void conv_gather_dma_kernel(GatherConvArgs a, 
     if (j < JX) {
       const int m = m0 + row;
       if (m < Mtot) {
-        const int ow = m % a.OW, t2 = m / a.OW, oh = t2 % a.OH, n = t2 / a.OH;
+        const int ow = m % b.OW, t2 = m / b.OW, oh = t2 % b.OH, n = t2 / b.OH;
         const int ih0 = oh * a.in_stride, iw0 = ow * a.in_stride;
         hw[j] = (ih0 << 16) | iw0;
         src[j] = reinterpret_cast<const char*>(a.in) + (((size_t)n * a.Hi + ih0) * a.Wi + iw0) * (size_t)a.Ci * 2 + u * 16;
@@ -88,12 +96,12 @@ __global__ __launch_bounds__(256) void conv_gather_dma_kernel(GatherConvArgs a, 
   }
   const char* zero = reinterpret_cast<const char*>(g_zero_word);
   const int cpc = a.Ci >> 6;              // chunks per tap
-  const int nchunks = a.ntaps * cpc;
+  const int nchunks = b.ntaps * cpc;
 
   auto issue = [&](int kc) {
     unsigned char* stage = smem + (size_t)(kc % STAGES) * (R * ROWB);
     const int tapi = kc / cpc, cb = (kc - tapi * cpc) * 128;   // byte offset of the 64-channel block
-    const int tp = a.tap[tapi];
+    const int tp = a.nclass > 1 ? a.ctap[cls][tapi] : a.tap[tapi];
     const int dh = (tp & 0xff) - 8, dw = ((tp >> 8) & 0xff) - 8, kofs = tp >> 16;
     const long xoff = ((long)dh * a.Wi + dw) * a.Ci * 2 + cb;
     const long woff = (long)kofs * a.Ci * 2 + cb;
@@ -156,7 +164,7 @@ __global__ __launch_bounds__(256) void conv_gather_dma_kernel(GatherConvArgs a, 
     }
   }
   wait_vmcnt<0>();
-  combine_and_store32<FN, BN>(a, acc, m0, c0, wave_m, wk, lane, smem);
+  combine_and_store32<FN, BN>(b, acc, m0, c0, wave_m, wk, lane, smem);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -485,16 +493,33 @@ static hipError_t run_wide(const GatherConvArgs& a, hipStream_t s) {
     if (e != hipSuccess) return e;
     configured = true;
   }
-  const int Mtot = a.N * a.OH * a.OW;
-  const int m_tiles = (Mtot + 127) / 128, n_tiles = (a.Co + BN - 1) / BN;
+  const int n_tiles = (a.Co + BN - 1) / BN;
   static char name[64];
   if (!name[0]) snprintf(name, sizeof(name), "conv_gather_dma_kernel<%d, %d>", BN, STAGES);
   note_kernel(name);
+  if (a.nclass > 1) {
+    GatherConvArgs m = a;
+    int tiles = 0;
+    for (int i = 0; i < a.nclass; ++i) {
+      m.cls_start[i] = tiles;
+      tiles += (a.N * a.cOH[i] * a.cOW[i] + 127) / 128 * n_tiles;
+    }
+    m.cls_start[a.nclass] = tiles;
+    if (tiles <= 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((conv_gather_dma_kernel<BN, STAGES>), dim3(tiles), dim3(256), lds, s, m, 0, n_tiles);
+    return hipGetLastError();
+  }
+  const int Mtot = a.N * a.OH * a.OW;
+  const int m_tiles = (Mtot + 127) / 128;
   hipLaunchKernelGGL((conv_gather_dma_kernel<BN, STAGES>), dim3(m_tiles * n_tiles), dim3(256), lds, s, a, m_tiles, n_tiles);
   return hipGetLastError();
 }
 
 hipError_t launch_conv_gather_wide(const GatherConvArgs& a, hipStream_t s) {
+  if (a.nclass > 1) {   // the caller has checked conv_gather_wide_applies on the common fields
+    if (a.nclass > 4 || a.Ci % 64 != 0 || a.Co < 128) return hipErrorInvalidValue;
+    return a.Co % 160 == 0 ? run_wide<160, 4>(a, s) : run_wide<128, 4>(a, s);
+  }
   if (!conv_gather_wide_applies(a) || a.N * a.OH * a.OW <= 0) return hipErrorInvalidValue;
   static const bool no_patch = getenv("FDG_NO_PATCH") != nullptr;
   if (conv_patch_applies(a) && !no_patch) return a.Co % 160 == 0 ? run_patch_rows<160>(a, s) : run_patch_rows<128>(a, s);

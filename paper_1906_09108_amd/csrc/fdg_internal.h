@@ -34,6 +34,14 @@ struct GatherConvArgs {
   int Kw;                // weight row pitch in elements
   int ntaps;
   int tap[9];
+  // Several output geometries in one launch (the four parity classes of a stride-2 data gradient), wide
+  // kernel only.  nclass <= 1: the single geometry above.  Otherwise class i owns the tiles cls_start[i] ..
+  // cls_start[i+1]-1 and replaces OH, OW, ooh, oow, ntaps and the tap list (a class may have no tap at all:
+  // its outputs are the addend, or zero).
+  int nclass;
+  int cls_start[5];
+  int cOH[4], cOW[4], cooh[4], coow[4], cntaps[4];
+  int ctap[4][4];
 };
 hipError_t launch_conv_gather(const GatherConvArgs& a, hipStream_t s);
 
