@@ -287,5 +287,8 @@ hipError_t launch_conv_wgrad_wide(const WgradArgs& a, hipStream_t s);
 // The same for channel counts that are multiples of 128: 128 x 128 blocks, contraction split over the waves.
 bool conv_wgrad128_applies(const WgradArgs& a);
 hipError_t launch_conv_wgrad128(const WgradArgs& a, hipStream_t s);
+// Output channels a multiple of 320, input channels a multiple of 64: 320 x 64 blocks.
+bool conv_wgrad_tall_applies(const WgradArgs& a);
+hipError_t launch_conv_wgrad_tall(const WgradArgs& a, hipStream_t s);
 
 }  // namespace fdg

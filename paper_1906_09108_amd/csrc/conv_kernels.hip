@@ -341,6 +341,7 @@ hipError_t launch_conv_wgrad(const WgradArgs& a, hipStream_t s) {
     return hipErrorInvalidValue;
   static const bool old_wide = getenv("FDG_WGRAD_160") != nullptr;   // A/B switch for measurements
   if (conv_wgrad128_applies(a) && !(old_wide && conv_wgrad_wide_applies(a))) return launch_conv_wgrad128(a, s);
+  if (conv_wgrad_tall_applies(a) && !(old_wide && conv_wgrad_wide_applies(a))) return launch_conv_wgrad_tall(a, s);
   if (conv_wgrad_wide_applies(a)) return launch_conv_wgrad_wide(a, s);
   if (a.overwrite) {   // the kernels below only add (atomics)
     hipError_t e = launch_fill_f32(a.dw, (size_t)a.Co * a.ntaps * a.Ci, 0.f, s);
@@ -450,7 +451,7 @@ size_t conv_wgrad_scratch_bytes(const ConvShape& c) {
   WgradArgs a{};
   a.Co = c.Co; a.Ci = c.Ci; a.Cx = c.Cip; a.OW = c.Wo(); a.ntaps = c.T;
   a.N = c.N; a.OH = c.Ho(); a.Hi = c.Hi; a.Wi = c.Wi; a.stride = c.stride;
-  return (conv_wgrad_wide_applies(a) || conv_wgrad128_applies(a)) ? (size_t)8 * c.Co * c.T * c.Ci * 4 : 0;
+  return (conv_wgrad_wide_applies(a) || conv_wgrad128_applies(a) || conv_wgrad_tall_applies(a)) ? (size_t)8 * c.Co * c.T * c.Ci * 4 : 0;
 }
 
 hipError_t conv_wgrad(const ConvShape& c, const bf16_t* x, const bf16_t* dy, float* dw, float* scratch,

@@ -1070,6 +1070,322 @@ hipError_t launch_conv_wgrad128(const WgradArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------------
+// Weight gradient, 320 x 64 blocks (the 320-channel layers: 320 = 5 * 64 has no 128-wide tiling)
+// ------------------------------------------------------------------------------------------------
+// The same scheme as the 128 x 128 kernel with another shape: the block is 320 output channels x 64 input
+// channels of one tap, wave_m = wave & 1 owns 160 output channels (5 fragments of dy) and all 64 input channels
+// (2 fragments of x): 10 accumulator blocks, 7 fragment reads per 10 MFMAs.  A 64-pixel chunk of such a block
+// would be 48 KB, too few stages for the LDS, so a chunk is 32 pixels (24 KB per stage) and each wave (wk =
+// wave >> 1) takes ONE 16-pixel step of it; the fragments of chunk c+1 are read during the MFMAs of chunk c.
+// Rows are 640 bytes (dy) and 128 bytes (x): the row pitch is 4 mod 8 slots of 32 bytes, so pixels p and p+2
+// start in the same banks and the slot is XORed with 2 * ((pixel >> 1) & 1).
+template <int STAGES>
+__global__ __launch_bounds__(256) void conv_wgrad_tall_kernel(WgradArgs a, Wgrad128Launch L) {
+  constexpr int TA = 320, TB = 64, BKP = 32;
+  constexpr int ROWA = TA * 2, ROWBB = TB * 2, PARTA = BKP * ROWA, PARTB = BKP * ROWBB, STAGE = PARTA + PARTB;
+  constexpr int UA = TA / 8, UB = TB / 8;                  // 16-byte units per row
+  constexpr int JA = BKP * UA / 256, JB = BKP * UB / 256, NJ = JA + JB;
+  constexpr int FA = 5, FB = 2, NF = FA + FB, NM = FA * FB;
+  static_assert(BKP * UA % 256 == 0 && BKP * UB % 256 == 0, "whole load instructions");
+  static_assert(STAGES >= 4 && (STAGES - 2) * NJ < 64, "pipeline depth / vmcnt range");
+  static_assert(STAGES * STAGE >= 4 * FA * 16 * 256, "room for the exchange of the partial blocks");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // STAGES * STAGE
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave_m = wave & 1, wk = wave >> 1;
+
+  int t = blockIdx.x;
+  const int total = gridDim.x;
+  if ((total & 7) == 0) t = (blockIdx.x & 7) * (total >> 3) + (blockIdx.x >> 3);
+  const int ci_t = t % L.ci_tiles; t /= L.ci_tiles;
+  const int co_t = t % L.co_tiles; t /= L.co_tiles;
+  const int tapi = t % a.ntaps;
+  const int split = t / a.ntaps;
+  const int co0 = co_t * TA, ci0 = ci_t * TB;
+  const int tp = a.tap[tapi];
+  const int dh = (tp & 0xff) - 8, dw = ((tp >> 8) & 0xff) - 8;
+  const int total_chunks = (a.N * a.OH * a.OW) / BKP;
+  const int chunk_lo = split * L.chunks_per_split;
+  const int n = min(total_chunks, chunk_lo + L.chunks_per_split) - chunk_lo;
+  if (n <= 0) return;
+
+  // ---- per-thread DMA sources: instruction j of this wave covers the 64 units 64*(4j+wave) .. of a tile ----
+  const char* aptr[JA];
+  const char* bptr[JB];
+  unsigned bmask[JB];
+#pragma unroll
+  for (int j = 0; j < JA; ++j) {
+    const int P = 64 * (4 * j + wave) + lane;
+    const int r = P / UA, up = P % UA;
+    const int u = 2 * ((up >> 1) ^ (2 * ((r >> 1) & 1))) + (up & 1);
+    aptr[j] = reinterpret_cast<const char*>(a.dy) + ((size_t)(chunk_lo * BKP + r) * a.Co + co0 + u * 8) * 2;
+  }
+#pragma unroll
+  for (int j = 0; j < JB; ++j) {
+    const int P = 64 * (4 * j + wave) + lane;
+    const int r = P / UB, up = P % UB;
+    const int u = 2 * ((up >> 1) ^ (2 * ((r >> 1) & 1))) + (up & 1);
+    const int m = chunk_lo * BKP + r;
+    const int ow = m % a.OW, t2 = m / a.OW, oh = t2 % a.OH, nimg = t2 / a.OH;
+    const int iw = ow * a.stride + dw;
+    const bool colok = (unsigned)iw < (unsigned)a.Wi;
+    bptr[j] = reinterpret_cast<const char*>(a.x) +
+              ((((long long)nimg * a.Hi + oh * a.stride + dh) * a.Wi + iw) * a.Cx + ci0 + u * 8) * 2;
+    unsigned mask = 0;
+    int ohq = oh;
+    for (int q = 0; q < L.period; ++q) {
+      if (colok && (unsigned)(ohq * a.stride + dh) < (unsigned)a.Hi) mask |= 1u << q;
+      ohq += L.d_oh;
+      if (ohq >= a.OH) ohq -= a.OH;
+    }
+    bmask[j] = mask;
+  }
+  const char* zero = reinterpret_cast<const char*>(g_zero_word);
+
+  int issue_phase = 0;   // (chunk being issued) mod period
+  auto issue_one = [&](int d, int c) {   // piece d of chunk c (relative to chunk_lo)
+    unsigned char* stage = smem + (size_t)(c % STAGES) * STAGE;
+    if (d < JA) {
+      dma16(aptr[d] + (long long)c * L.a_step, stage + (64 * (4 * d + wave)) * 16);
+    } else {
+      const int j = d - JA;
+      const bool ok = (bmask[j] >> issue_phase) & 1u;
+      const uint64_t pa = (uint64_t)(bptr[j] + (long long)c * L.b_step), pz = (uint64_t)zero;
+      const uint32_t lo = ok ? (uint32_t)pa : (uint32_t)pz, hi = ok ? (uint32_t)(pa >> 32) : (uint32_t)(pz >> 32);
+      dma16((const char*)(((uint64_t)hi << 32) | lo), stage + PARTA + (64 * (4 * j + wave)) * 16);
+    }
+  };
+  auto issue_done = [&]() { issue_phase = issue_phase + 1 == L.period ? 0 : issue_phase + 1; };
+
+  f32x16 acc[FA][FB];
+#pragma unroll
+  for (int i = 0; i < FA; ++i)
+#pragma unroll
+    for (int j = 0; j < FB; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // ---- operand reads (see the 128 x 128 kernel): lane group g = lane >> 4 takes channels 16*(g&1).. of a
+  //      32-channel block and pixels 8*(g>>1) .. +7 of this wave's 16 ----
+  int aoff[FA], boff[FB];
+  {
+    const int g = lane >> 4, i16 = lane & 15;
+    const int prow = 16 * wk + 8 * (g >> 1) + (i16 >> 2);
+    const int x = 2 * (((i16 >> 2) >> 1) & 1);
+#pragma unroll
+    for (int f = 0; f < FA; ++f)
+      aoff[f] = prow * ROWA + (i16 & 3) * 8 + (((2 * (FA * wave_m + f) + (g & 1)) ^ x) * 32);
+#pragma unroll
+    for (int f = 0; f < FB; ++f) boff[f] = PARTA + prow * ROWBB + (i16 & 3) * 8 + (((2 * f + (g & 1)) ^ x) * 32);
+  }
+  const unsigned lds0 = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)smem);
+  // fragment position in issue order = the order the MFMAs (K = FB i + j) need them: A0, B0, B1, A1, ..., A4
+  v4s16 flo[2][NF], fhi[2][NF];   // index: F < FA: dy fragment F; else x fragment F - FA
+  auto read_one = [&](auto set_tag, auto idx_tag, int c) {
+    constexpr int S = decltype(set_tag)::value, IDX = decltype(idx_tag)::value;
+    constexpr int POS = IDX >> 1, H = IDX & 1;
+    constexpr int F = POS == 0 ? 0 : (POS <= FB ? FA + POS - 1 : POS - FB);
+    int off;
+    if constexpr (F < FA) off = aoff[F]; else off = boff[F - FA];
+    const unsigned addr = lds0 + (unsigned)(c % STAGES) * STAGE + off;
+    v4s16& v = H == 0 ? flo[S][F] : fhi[S][F];
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "i"(H * 4 * (F < FA ? ROWA : ROWBB)));
+  };
+  // Before MFMA K the fragments it is the first to use have landed when at most N reads are outstanding.
+  auto before_mma = [&](auto set_tag, auto k_tag, auto n_tag) {
+    constexpr int S = decltype(set_tag)::value, K = decltype(k_tag)::value, N = decltype(n_tag)::value;
+    static_assert(N >= 0 && N <= 15, "lgkmcnt range");
+    if constexpr (K == 0) {
+      v4s16 &l0 = flo[S][0], &h0 = fhi[S][0], &l1 = flo[S][FA], &h1 = fhi[S][FA];
+      asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(l0), "+v"(h0), "+v"(l1), "+v"(h1) : "n"(N));
+    } else if constexpr (K < FB) {
+      v4s16 &l0 = flo[S][FA + K], &h0 = fhi[S][FA + K];
+      asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(l0), "+v"(h0) : "n"(N));
+    } else if constexpr (K % FB == 0) {
+      v4s16 &l0 = flo[S][K / FB], &h0 = fhi[S][K / FB];
+      asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(l0), "+v"(h0) : "n"(N));
+    }
+  };
+  auto needed = [](int K) constexpr { return K < FB ? K + 2 : FB + 1 + K / FB; };   // fragments used up to MFMA K
+  auto frag = [&](auto set_tag, int f) {
+    constexpr int S = decltype(set_tag)::value;
+    typedef short v8s16 __attribute__((ext_vector_type(8)));
+    const v8s16 both = __builtin_shufflevector(flo[S][f], fhi[S][f], 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, both);
+  };
+  auto mma_one = [&](auto set_tag, auto k_tag) {
+    constexpr int K = decltype(k_tag)::value;
+    acc[K / FB][K % FB] = mfma32(frag(set_tag, K / FB), frag(set_tag, FA + K % FB), acc[K / FB][K % FB]);
+  };
+
+  // prologue: chunks 0 .. STAGES-2 in flight, chunk 0 visible, its fragments in set 0
+#pragma unroll
+  for (int p = 0; p < STAGES - 1; ++p)
+    if (p < n) {
+#pragma unroll
+      for (int d = 0; d < NJ; ++d) issue_one(d, p);
+      issue_done();
+    }
+  // chunk 0 has landed when at most the chunks issued after it are outstanding: min(n, STAGES-1) - 1 of them
+  static_for<STAGES - 1>([&](auto q_tag) {
+    constexpr int Q = decltype(q_tag)::value;   // chunks after chunk 0
+    if ((n < STAGES - 1 ? n : STAGES - 1) - 1 == Q) wait_vmcnt<Q * NJ>();
+  });
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  using set0 = std::integral_constant<int, 0>;
+  using set1 = std::integral_constant<int, 1>;
+  static_for<2 * NF>([&](auto idx) { read_one(set0{}, idx, 0); });
+
+  // One chunk = NM (MFMA, piece) slots on one fragment set.  After slot 1: barrier c+1 (chunk c+1 visible,
+  // everybody done reading chunk c-1).  Slots 2 .. NF+1: the reads of chunk c+1 into the other set, two per
+  // slot.  Slots 2 ..: the NJ loads of chunk c+STAGES-1 into the stage of chunk c-1, one per slot.
+  // Whether a next chunk exists and whether there is still something to load are run-time (wave-uniform)
+  // conditions, and the fragment set alternates at compile time (the loop below takes chunks in pairs): a
+  // run-time choice of the set makes the compiler shuffle all accumulators between the two variants.
+  static_assert(NF + 2 <= NM && NJ + 2 <= NM, "slots of a chunk");
+  auto step = [&](auto set_tag, int c) {
+    constexpr int S = decltype(set_tag)::value;
+    using other = std::integral_constant<int, 1 - S>;
+    const bool next = c + 1 < n, issue = c + STAGES - 1 < n;
+    static_for<NM>([&](auto k) {
+      constexpr int K = decltype(k)::value;
+      if constexpr (K < FB || K % FB == 0) {
+        // reads of the other set issued meanwhile: two per slot from slot 2 on (only when there is a next chunk;
+        // without one fewer are outstanding and the bound below is merely not tight)
+        constexpr int NEWER = K > 2 ? 2 * ((K - 2) < NF ? (K - 2) : NF) : 0;
+        before_mma(set_tag, k, std::integral_constant<int, 2 * (NF - needed(K)) + NEWER>{});
+      }
+      mma_one(set_tag, k);
+      if (next) {
+        if constexpr (K == 1) {
+          // chunk c+1 has landed when only the chunks issued after it are outstanding; once nothing is issued
+          // any more, simply wait for everything
+          if (issue) wait_vmcnt<(STAGES - 3) * NJ>(); else wait_vmcnt<0>();
+          asm volatile("" ::: "memory");
+          __builtin_amdgcn_s_barrier();
+          asm volatile("" ::: "memory");
+        }
+        if constexpr (K >= 2 && K - 2 < NF) {
+          read_one(other{}, std::integral_constant<int, 2 * (K - 2)>{}, c + 1);
+          read_one(other{}, std::integral_constant<int, 2 * (K - 2) + 1>{}, c + 1);
+        }
+      }
+      if constexpr (K >= 2 && K - 2 < NJ) {
+        if (issue) issue_one(K - 2, c + STAGES - 1);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    if (issue) issue_done();
+  };
+  {
+    int c = 0;
+    for (; c + 1 < n; c += 2) {
+      step(set0{}, c);
+      step(set1{}, c + 1);
+    }
+    if (c < n) step(set0{}, c);
+  }
+
+  // ---- add the two pixel halves: wave (wave_m, wk) keeps input-channel block wk of its two and receives its
+  //      partner's sums for it ----
+  wait_vmcnt<0>();
+  __syncthreads();
+  f32x4* mine = reinterpret_cast<f32x4*>(smem) + (size_t)wave * (FA * 4 * 64);
+  const f32x4* theirs = reinterpret_cast<const f32x4*>(smem) + (size_t)(wave ^ 2) * (FA * 4 * 64);
+  f32x16 keep[FA];
+#pragma unroll
+  for (int i = 0; i < FA; ++i) {
+    const f32x16 give = wk == 0 ? acc[i][1] : acc[i][0];
+    keep[i] = wk == 0 ? acc[i][0] : acc[i][1];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      mine[(i * 4 + g) * 64 + lane] = f32x4{give[4 * g], give[4 * g + 1], give[4 * g + 2], give[4 * g + 3]};
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < FA; ++i)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const f32x4 p = theirs[(i * 4 + g) * 64 + lane];
+      keep[i][4 * g] += p[0]; keep[i][4 * g + 1] += p[1]; keep[i][4 * g + 2] += p[2]; keep[i][4 * g + 3] += p[3];
+    }
+  // D block i: lane holds column ci = 32 wk + (lane & 31), rows co = 32 i + 8 (v >> 2) + 4 (lane >> 5) + (v & 3)
+  float* dst = L.partial ? L.partial + (size_t)split * L.split_stride : a.dw;
+  const int mode = (L.partial || (L.splits == 1 && a.overwrite)) ? 0 : (L.splits > 1 ? 1 : 2);
+  const int ntaps = a.ntaps, Ci = a.Ci;
+  const int ci = ci0 + 32 * wk + (lane & 31);
+  const int co_base = co0 + 160 * wave_m + 4 * (lane >> 5);
+#pragma unroll
+  for (int i = 0; i < FA; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int co = co_base + 32 * i + 8 * (v >> 2) + (v & 3);
+      float* o = dst + ((size_t)co * ntaps + tapi) * Ci + ci;
+      const float val = keep[i][v];
+      if (mode == 0) *o = val;
+      else if (mode == 1) atomicAdd(o, val);
+      else *o += val;
+    }
+}
+
+bool conv_wgrad_tall_applies(const WgradArgs& a) {
+  if (a.Co % 320 != 0 || a.Ci % 64 != 0 || a.Cx != a.Ci || a.ntaps < 1) return false;
+  if (a.OW < 1 || 32 % a.OW != 0 || (a.N * a.OH * a.OW) % 32 != 0 || a.OH > 32) return false;
+  return a.Hi == a.stride * a.OH;
+}
+
+hipError_t launch_conv_wgrad_tall(const WgradArgs& a, hipStream_t s) {
+  if (!conv_wgrad_tall_applies(a) || a.N * a.OH * a.OW <= 0) return hipErrorInvalidValue;
+  constexpr int STAGES = 4;   // 4 x 24 KB (deeper rings measured slower)
+  constexpr size_t lds = (size_t)STAGES * 32 * (640 + 128);
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad_tall_kernel<STAGES>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int total_chunks = a.N * a.OH * a.OW / 32;
+  Wgrad128Launch L;
+  L.co_tiles = a.Co / 320;
+  L.ci_tiles = a.Ci / 64;
+  const int tiles = L.co_tiles * L.ci_tiles * a.ntaps;
+  const size_t elems = (size_t)a.Co * a.ntaps * a.Ci;
+  const int max_by_scratch = a.scratch ? (int)(a.scratch_bytes / (elems * 4)) : 0;
+  int S = 1;
+  if (tiles <= 128 && max_by_scratch >= 2) {
+    S = 256 / tiles;
+    if (S > max_by_scratch) S = max_by_scratch;
+    if (S > total_chunks / 16) S = total_chunks / 16;
+    if (S < 1) S = 1;
+  }
+  L.chunks_per_split = (total_chunks + S - 1) / S;
+  L.splits = (total_chunks + L.chunks_per_split - 1) / L.chunks_per_split;
+  L.partial = L.splits > 1 ? a.scratch : nullptr;
+  L.split_stride = elems;
+  const int d_oh_full = 32 / a.OW;
+  L.d_oh = d_oh_full % a.OH;
+  int g = L.d_oh == 0 ? a.OH : L.d_oh, h = a.OH;   // gcd(d_oh, OH)
+  while (h) { const int r = g % h; g = h; h = r; }
+  L.period = a.OH / g;
+  L.a_step = (long long)32 * a.Co * 2;
+  L.b_step = (long long)d_oh_full * a.stride * a.Wi * a.Cx * 2;
+  note_kernel("conv_wgrad_tall_kernel<4>");
+  hipLaunchKernelGGL((conv_wgrad_tall_kernel<STAGES>), dim3(tiles * L.splits), dim3(256), lds, s, a, L);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || !L.partial) return e;
+  const size_t n4 = elems / 4;
+  size_t blocks = (n4 + 255) / 256;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, s, reinterpret_cast<float4*>(a.dw),
+                     reinterpret_cast<const float4*>(a.scratch), n4, L.splits, elems / 4, a.overwrite);
+  return hipGetLastError();
+}
+
 bool conv_wgrad_wide_applies(const WgradArgs& a) {
   return a.Co % 160 == 0 && a.Ci % 160 == 0 && a.Cx == a.Ci && a.OW >= 1 && 64 % a.OW == 0 && a.ntaps >= 1;
 }
