@@ -197,12 +197,12 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
   static_assert(BN % 32 == 0 && PR % 32 == 0, "whole DMA instructions and 32x32 blocks");
   constexpr int JX = PR / 32, JW = BN / 32;
   constexpr int FM = 2, FN = BN / 32;
-  constexpr int XBYTES = PR * ROWB, WBYTES = BN * ROWB;
-  constexpr int ZOFF = 2 * XBYTES + WS * WBYTES;   // 256 bytes of zeros
+  constexpr int XBYTES = PR * ROWB + 256, WBYTES = BN * ROWB;   // a patch buffer ends with two rows of zeros
+  constexpr int LDS_BYTES = 2 * XBYTES + WS * WBYTES;
   static_assert((WS - 2) * JW + JX < 64, "vmcnt range");
   static_assert(WS >= 3 && WS <= 9, "pipeline depth");
-  static_assert((size_t)ZOFF >= (size_t)4 * FN * 16 * 256 && (size_t)ZOFF >= (size_t)4 * out_stage_bytes(BN), "room for the output stage");
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // ZOFF + 256
+  static_assert((size_t)LDS_BYTES >= (size_t)4 * FN * 16 * 256 && (size_t)LDS_BYTES >= (size_t)4 * out_stage_bytes(BN), "room for the output stage");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // LDS_BYTES
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -215,41 +215,41 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
   if ((total & 7) == 0) t = (blockIdx.x & 7) * (total >> 3) + (blockIdx.x >> 3);
   const int m0 = (t / n_tiles) * BM, c0 = (t % n_tiles) * BN;
 
-  if (tid < 16) reinterpret_cast<uint4*>(smem + ZOFF)[tid] = make_uint4(0u, 0u, 0u, 0u);   // visible after the first barrier
+  if (tid < 32)   // the zero rows of both patch buffers; visible after the first barrier
+    reinterpret_cast<uint4*>(smem + (tid >> 4) * XBYTES + PR * ROWB)[tid & 15] = make_uint4(0u, 0u, 0u, 0u);
 
-  // ---- per-thread DMA sources ----
-  const char* zero = reinterpret_cast<const char*>(g_zero_word);
-  const char* xsrc[JX];   // this thread's 16 bytes of patch row p at channel block 0, or null
-  const char* wsrc[JW];   // this thread's 16 bytes of weight row at k = 0, or null
+  // ---- per-thread DMA sources as 32-bit offsets from a wave-uniform base (the address then needs no vector
+  //      arithmetic).  Rows that do not exist (patch rows before the first or after the last pixel, weight
+  //      rows past the last channel of a ragged tile) read some row that does: nothing valid refers to them. ----
+  unsigned xoff[JX], woff[JW];
 #pragma unroll
   for (int j = 0; j < JX; ++j) {
     const int p = 8 * (4 * j + wave) + (lane >> 3);
     const int u = (lane & 7) ^ ((p >> 1) & 7);
-    const int q = m0 - W - 1 + p;
-    xsrc[j] = (q >= 0 && q < Mtot) ? reinterpret_cast<const char*>(a.in) + (size_t)q * a.Ci * 2 + u * 16 : nullptr;
+    int q = m0 - W - 1 + p;
+    q = q < 0 ? 0 : (q >= Mtot ? Mtot - 1 : q);
+    xoff[j] = (unsigned)q * (unsigned)(a.Ci * 2) + u * 16;
   }
 #pragma unroll
   for (int j = 0; j < JW; ++j) {
     const int row = 8 * (4 * j + wave) + (lane >> 3);
     const int u = (lane & 7) ^ ((row >> 1) & 7);
-    const int c = c0 + row;
-    wsrc[j] = c < a.w_rows ? reinterpret_cast<const char*>(a.w) + (size_t)c * a.Kw * 2 + u * 16 : nullptr;
+    int c = c0 + row;
+    c = c >= a.w_rows ? a.w_rows - 1 : c;
+    woff[j] = (unsigned)c * (unsigned)(a.Kw * 2) + u * 16;
   }
-  int tdh[9], tdw[9], tko[9];
+  int tko[9];
 #pragma unroll
-  for (int i = 0; i < 9; ++i) {
-    const int tp = a.tap[i];
-    tdh[i] = (tp & 0xff) - 8;
-    tdw[i] = ((tp >> 8) & 0xff) - 8;
-    tko[i] = (tp >> 16) * a.Ci * 2;   // byte offset of the tap's k block in a weight row
-  }
+  for (int i = 0; i < 9; ++i) tko[i] = (a.tap[i] >> 16) * a.Ci * 2;   // byte offset of the tap's k block in a weight row
   const int cpc = a.Ci >> 6;   // channel blocks
 
   auto issue_x_one = [&](int j, int c) {
-    dma16(xsrc[j] ? xsrc[j] + c * 128 : zero, smem + (c & 1) * XBYTES + (8 * (4 * j + wave)) * ROWB);
+    const char* base = reinterpret_cast<const char*>(a.in) + (size_t)c * 128;
+    dma16(base + (size_t)xoff[j], smem + (c & 1) * XBYTES + (8 * (4 * j + wave)) * ROWB);
   };
   auto issue_w_one = [&](int j, int slot, int kbyte) {
-    dma16(wsrc[j] ? wsrc[j] + kbyte : zero, smem + 2 * XBYTES + slot * WBYTES + (8 * (4 * j + wave)) * ROWB);
+    const char* base = reinterpret_cast<const char*>(a.w) + (size_t)kbyte;
+    dma16(base + (size_t)woff[j], smem + 2 * XBYTES + slot * WBYTES + (8 * (4 * j + wave)) * ROWB);
   };
   f32x16 acc[FN][FM];
 #pragma unroll
@@ -259,27 +259,33 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // this lane's pixels (operand B columns) and weight rows (operand A rows)
-  int prow[FM], poh[FM], pow_[FM];
+  // ---- LDS addresses of this lane's operand fragments, computed once ----
+  // pixels (operand B): for every tap, pixel block and 16-channel step the address inside patch buffer 0 -- the
+  // shifted patch row, or a zero row at the same bank position when the tap falls outside the image; the
+  // whole table moves by +-XBYTES when the channel block changes buffers.
+  // weights (operand A): one address per 16-channel step; blocks are 4096 bytes apart (an immediate offset).
+  const unsigned lds0 = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)smem);
+  unsigned xaddr[9][FM][2], wlane[2];
 #pragma unroll
   for (int f = 0; f < FM; ++f) {
     const int r = wave_m * 64 + f * 32 + (lane & 31);
     const int m = m0 + r;
-    prow[f] = r + W + 1;
-    if (m < Mtot) {
-      pow_[f] = m % a.OW;
-      poh[f] = (m / a.OW) % a.OH;
-    } else {
-      pow_[f] = poh[f] = -4;   // every tap falls outside
+    const bool inside = m < Mtot;
+    const int ow = m % a.OW, oh = (m / a.OW) % a.OH;
+#pragma unroll
+    for (int i = 0; i < 9; ++i) {
+      const int dh = (a.tap[i] & 0xff) - 8, dw = ((a.tap[i] >> 8) & 0xff) - 8;
+      const int p = r + W + 1 + dh * W + dw;
+      const bool ok = inside && (unsigned)(oh + dh) < (unsigned)H && (unsigned)(ow + dw) < (unsigned)W;
+      const int rowoff = ok ? p * ROWB : (PR + (p & 1)) * ROWB;
+#pragma unroll
+      for (int ss = 0; ss < 2; ++ss)
+        xaddr[i][f][ss] = lds0 + rowoff + (((4 * wk + 2 * ss + (lane >> 5)) ^ ((p >> 1) & 7)) << 4);
     }
   }
-  int wrow_off[FN], wrow_swz[FN];
 #pragma unroll
-  for (int f = 0; f < FN; ++f) {
-    const int row = f * 32 + (lane & 31);
-    wrow_off[f] = row * ROWB;
-    wrow_swz[f] = (row >> 1) & 7;
-  }
+  for (int ss = 0; ss < 2; ++ss)
+    wlane[ss] = lds0 + 2 * XBYTES + (lane & 31) * ROWB + (((4 * wk + 2 * ss + (lane >> 5)) ^ (((lane & 31) >> 1) & 7)) << 4);
 
 #pragma unroll
   for (int j = 0; j < JX; ++j) issue_x_one(j, 0);
@@ -300,25 +306,21 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
   // lgkmcnt <= (fragments of the set still to come) + (fragments of the other set issued meanwhile).
   typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
   u32x4 fa[2][FN], fb[2][FM];
-  const unsigned lds0 = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)smem);
   // fragment idx of a half step in the order the MFMAs need them: B0, A0, B1, A1, A2, ...
-  auto read_one = [&](auto set_tag, auto idx_tag, int wslot, int xbuf, auto tap_tag, int ss) {
+  // wcur: this lane's weight address for the step's stage and 16-channel step; xshift: 0, or the distance to
+  // the other patch buffer when the fragment belongs to the next channel block.
+  auto read_one = [&](auto set_tag, auto idx_tag, unsigned wcur, auto tap_tag, auto ss_tag, int xshift) {
     constexpr int S = decltype(set_tag)::value, IDX = decltype(idx_tag)::value, T = decltype(tap_tag)::value;
-    const int u = 4 * wk + 2 * ss + (lane >> 5);
+    constexpr int SS = decltype(ss_tag)::value;
     if constexpr (IDX == 0 || IDX == 2) {
       constexpr int f = IDX / 2;
-      // patch row of this tap, or the zero region (same bank position, so it never adds a conflict)
-      const int p = prow[f] + tdh[T] * W + tdw[T];
-      const bool ok = (unsigned)(poh[f] + tdh[T]) < (unsigned)H && (unsigned)(pow_[f] + tdw[T]) < (unsigned)W;
-      const int off = ok ? xbuf * XBYTES + p * ROWB : ZOFF + (p & 1) * ROWB;
       u32x4& dst = fb[S][f];
-      const unsigned addr = lds0 + off + ((u ^ ((p >> 1) & 7)) << 4);
+      const unsigned addr = xaddr[T][f][SS] + xshift;
       asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(addr));
     } else {
       constexpr int f = IDX == 1 ? 0 : IDX - 2;
       u32x4& dst = fa[S][f];
-      const unsigned addr = lds0 + 2 * XBYTES + wslot * WBYTES + wrow_off[f] + ((u ^ wrow_swz[f]) << 4);
-      asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(addr));
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(wcur), "i"(f * 32 * ROWB));
     }
   };
   // Before MFMA K (K = 2 i + j uses A_i and B_j): the fragments it is the first to use have landed when at
@@ -353,7 +355,10 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
-  static_for<NFRAG>([&](auto idx) { read_one(set0{}, idx, 0, 0, std::integral_constant<int, 0>{}, 0); });
+  using tap0 = std::integral_constant<int, 0>;
+  using ss0 = std::integral_constant<int, 0>;
+  using ss1 = std::integral_constant<int, 1>;
+  static_for<NFRAG>([&](auto idx) { read_one(set0{}, idx, wlane[0], tap0{}, ss0{}, 0); });
 
   // Loads are issued thinly: a step's group of loads -- the weights of step i + WS - 1 and, in the first XG steps
   // of a channel block, a share of the next block's patch -- goes out one load every other slot over the whole
@@ -373,10 +378,20 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
   int slot = 0;   // weight stage of the current step
   auto chunk_body = [&](int c, auto last_tag) {
     constexpr bool LAST = decltype(last_tag)::value;
+    const int to_other = (c & 1) ? -XBYTES : XBYTES;   // from this block's patch buffer to the other one
+    if (c > 0) {
+#pragma unroll
+      for (int i = 0; i < 9; ++i)
+#pragma unroll
+        for (int f = 0; f < FM; ++f)
+#pragma unroll
+          for (int ss = 0; ss < 2; ++ss) xaddr[i][f][ss] -= to_other;   // the table follows the block into its buffer
+    }
     static_for<9>([&](auto t_tag) {
       constexpr int T = decltype(t_tag)::value;
       const int nslot = slot == WS - 1 ? 0 : slot + 1;
       const int islot = slot == 0 ? WS - 1 : slot - 1;
+      const unsigned wcur1 = wlane[1] + slot * WBYTES, wnext0 = wlane[0] + nslot * WBYTES;
       constexpr bool MORE = !(LAST && T == 8);            // a next step exists
       constexpr int TT = T + WS - 1;                      // tap of the step whose weights are issued now
       constexpr bool ISSUE_W = TT < 9 || !LAST;
@@ -400,7 +415,7 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
         if constexpr (K <= 1 || K % 2 == 0)
           before_mma(set0{}, k, std::integral_constant<int, left_after(K) + (K < NFRAG ? K : NFRAG)>{});
         mma_one(set0{}, k);
-        if constexpr (K < NFRAG) read_one(set1{}, k, slot, c & 1, t_tag, 1);
+        if constexpr (K < NFRAG) read_one(set1{}, k, wcur1, t_tag, ss1{}, 0);
         if constexpr (MORE && K == 1) {
           constexpr int PENDING = (WS >= 4 ? gsize(T - 1, LAST) : 0) + (WS >= 5 ? gsize(T - 2, LAST) : 0) +
                                   (WS >= 6 ? gsize(T - 3, LAST) : 0) + (WS >= 7 ? gsize(T - 4, LAST) : 0);
@@ -422,8 +437,8 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
         mma_one(set1{}, k);
         if constexpr (MORE) {
           if constexpr (K >= 2 && K - 2 < NFRAG) {
-            if constexpr (T < 8) read_one(set0{}, std::integral_constant<int, K - 2>{}, nslot, c & 1, std::integral_constant<int, (T + 1) % 9>{}, 0);
-            else read_one(set0{}, std::integral_constant<int, K - 2>{}, nslot, (c + 1) & 1, std::integral_constant<int, 0>{}, 0);
+            if constexpr (T < 8) read_one(set0{}, std::integral_constant<int, K - 2>{}, wnext0, std::integral_constant<int, (T + 1) % 9>{}, ss0{}, 0);
+            else read_one(set0{}, std::integral_constant<int, K - 2>{}, wnext0, tap0{}, ss0{}, to_other);
           }
           issue_at(std::integral_constant<int, NM + K>{});
         }
@@ -443,6 +458,8 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
 static bool conv_patch_applies(const GatherConvArgs& a) {
   if (a.ntaps != 9 || a.in_stride != 1 || a.out_stride != 1 || a.ooh != 0 || a.oow != 0) return false;
   if (a.OH != a.Hi || a.OW != a.Wi || a.OHf != a.OH || a.OWf != a.OW || a.Wi > 32 || a.Wi < 1) return false;
+  if (a.w_rows != a.Co) return false;                                     // no rows of zeros inside the weight matrix
+  if ((long long)a.N * a.Hi * a.Wi * a.Ci * 2 >= (1ll << 32) || (long long)a.w_rows * a.Kw * 2 >= (1ll << 32)) return false;   // 32-bit load offsets
   for (int i = 0; i < 9; ++i) {
     const int dh = (a.tap[i] & 0xff) - 8, dw = ((a.tap[i] >> 8) & 0xff) - 8;
     if (dh < -1 || dh > 1 || dw < -1 || dw > 1) return false;
@@ -453,7 +470,7 @@ static bool conv_patch_applies(const GatherConvArgs& a) {
 template <int BN, int PR>
 static hipError_t run_patch(const GatherConvArgs& a, hipStream_t s) {
   constexpr int WS = 5;
-  constexpr size_t lds = (size_t)2 * PR * 128 + (size_t)WS * BN * 128 + 256;
+  constexpr size_t lds = (size_t)2 * (PR * 128 + 256) + (size_t)WS * BN * 128;
   static_assert(lds + 2 * BN * 4 <= 160 * 1024, "LDS of one compute unit");
   static bool configured = false;
   if (!configured) {
