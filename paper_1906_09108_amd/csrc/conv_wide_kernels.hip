@@ -251,6 +251,14 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
     const char* base = reinterpret_cast<const char*>(a.w) + (size_t)kbyte;
     dma16(base + (size_t)woff[j], smem + 2 * XBYTES + slot * WBYTES + (8 * (4 * j + wave)) * ROWB);
   };
+  // the first loads go out before the rest of the set-up, which then runs while they are in flight
+#pragma unroll
+  for (int j = 0; j < JX; ++j) issue_x_one(j, 0);
+#pragma unroll
+  for (int p = 0; p < WS - 1; ++p)   // 9 taps >= WS - 1 steps always exist
+#pragma unroll
+    for (int j = 0; j < JW; ++j) issue_w_one(j, p, tko[p]);
+
   f32x16 acc[FN][FM];
 #pragma unroll
   for (int i = 0; i < FN; ++i)
@@ -286,13 +294,6 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
 #pragma unroll
   for (int ss = 0; ss < 2; ++ss)
     wlane[ss] = lds0 + 2 * XBYTES + (lane & 31) * ROWB + (((4 * wk + 2 * ss + (lane >> 5)) ^ (((lane & 31) >> 1) & 7)) << 4);
-
-#pragma unroll
-  for (int j = 0; j < JX; ++j) issue_x_one(j, 0);
-#pragma unroll
-  for (int p = 0; p < WS - 1; ++p)   // 9 taps >= WS - 1 steps always exist
-#pragma unroll
-    for (int j = 0; j < JW; ++j) issue_w_one(j, p, tko[p]);
 
   // Operand fragments, two sets: while the MFMAs of one 16-channel half step run from one set, the reads of
   // the next half step fill the other, so LDS latency stays behind the matrix pipe even with one wave per
