@@ -119,16 +119,19 @@ __device__ __forceinline__ void store_tile(const GatherConvArgs& a, const f32x4 
 // Must be called by all threads of the workgroup (the statistics are combined through LDS).
 constexpr int out_stage_pitch(int BN) { return BN * 4 + 16; }
 constexpr int out_stage_bytes(int BN) { return 32 * out_stage_pitch(BN) + 128; }
+// where the lanes park their partial statistics: 4 waves x PERIOD x 64 lanes x 8 floats (PERIOD = 5 for 160 channels)
+constexpr int stats_stage_bytes(int BN) { return 4 * ((BN / 4) % 16 == 0 ? 1 : (BN / 4) / 8) * 64 * 32; }
 
 template <int FN, int BN>
 __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x16 (&acc)[FN], int m_base, int c_tile,
-                                             int lane, unsigned char* lds) {
+                                             int lane, unsigned char* lds, unsigned char* stats_lds) {
   static_assert(FN * 32 == BN, "one wave carries all channels of the tile");
   constexpr int PITCH = out_stage_pitch(BN);
   constexpr int UNITS = BN / 4;                       // 16-byte fp32 units per pixel
   constexpr int ITERS = 32 * UNITS / 64;
   constexpr int PERIOD = UNITS % 64 == 0 ? 1 : (UNITS % 32 == 0 ? 1 : (UNITS % 16 == 0 ? UNITS / 16 : (UNITS % 8 == 0 ? UNITS / 8 : UNITS)));
   static_assert((64 * PERIOD) % UNITS == 0 && ITERS % PERIOD == 0, "unit assignment repeats every PERIOD iterations");
+  static_assert(stats_stage_bytes(BN) == 4 * PERIOD * 64 * 32, "size of the statistics stage");
   const int Mtot = a.N * a.OH * a.OW;
   // The arguments live in constant memory, and a compiler short of scalar registers re-reads them at every
   // use: one scalar load and a full wait per pointer test, twenty times over.  Read what the row loop needs
@@ -223,25 +226,32 @@ __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x
     }
   }
   if (a.stats) {
-    // per-channel sums of the workgroup in LDS (LDS atomics: at most two lanes of an instruction share a
-    // channel), then one global atomic per channel and value
-    __shared__ float red[2 * BN];
-    __syncthreads();   // every wave has finished with the shared regions the caller may have overlapped
-    for (int t = threadIdx.x; t < 2 * BN; t += blockDim.x) red[t] = 0.f;
-    __syncthreads();
+    // Per-channel sums of the workgroup: every lane parks its partial sums in LDS, then one thread per channel
+    // and value adds the lanes that carried that channel (LDS float atomics would do the same in one step but
+    // run at a few lane operations per clock: 15-25 us per launch).
+    float* park = reinterpret_cast<float*>(stats_lds);
+    const int wave = threadIdx.x >> 6;
 #pragma unroll
     for (int k = 0; k < PERIOD; ++k) {
-      const int un = (k * 64 + lane) % UNITS;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        atomicAdd(&red[un * 4 + e], s1[k][e]);
-        atomicAdd(&red[BN + un * 4 + e], s2[k][e]);
-      }
+      f32x4* dst = reinterpret_cast<f32x4*>(park + (size_t)((wave * PERIOD + k) * 64 + lane) * 8);
+      dst[0] = f32x4{s1[k][0], s1[k][1], s1[k][2], s1[k][3]};
+      dst[1] = f32x4{s2[k][0], s2[k][1], s2[k][2], s2[k][3]};
     }
     __syncthreads();
     for (int t = threadIdx.x; t < 2 * BN; t += blockDim.x) {
-      const int c = c_tile + (t % BN);
-      if (c < a.Co) atomicAdd(a.stats + (t / BN) * a.Co + c, red[t]);
+      const int cl = t % BN, which = t / BN;
+      const int c = c_tile + cl;
+      if (c >= a.Co) continue;
+      const int un = cl >> 2, e = cl & 3;
+      float sum = 0.f;
+#pragma unroll
+      for (int k = 0; k < PERIOD; ++k) {
+        const int l0 = ((un - k * 64) % UNITS + UNITS) % UNITS;   // lanes with (k*64 + lane) % UNITS == un
+        for (int l = l0; l < 64; l += UNITS)
+#pragma unroll
+          for (int w = 0; w < 4; ++w) sum += park[(size_t)((w * PERIOD + k) * 64 + l) * 8 + which * 4 + e];
+      }
+      atomicAdd(a.stats + which * a.Co + c, sum);
     }
   }
 }
@@ -249,7 +259,8 @@ __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x
 // End of a wide kernel whose four waves are (wave_m, wk): wave_m owns 64 pixels as two 32-pixel blocks j, wk
 // one half of the contraction.  The two halves are added through LDS so that every wave ends with one
 // 32-pixel block (wave wk keeps block j = wk and receives its partner's), then all four run the output stage.
-// smem must hold max(4 * FN * 16 * 256, 4 * out_stage_bytes(BN)) bytes and be idle (no loads in flight).
+// smem must hold max(4 * FN * 16 * 256, 4 * out_stage_bytes(BN) + stats_stage_bytes(BN)) bytes and be idle (no loads
+// in flight).
 template <int FN, int BN>
 __device__ __forceinline__ void combine_and_store32(const GatherConvArgs& a, f32x16 (&acc)[FN][2], int m_tile, int c_tile,
                                                     int wave_m, int wk, int lane, unsigned char* smem) {
@@ -275,7 +286,8 @@ __device__ __forceinline__ void combine_and_store32(const GatherConvArgs& a, f32
     }
   __syncthreads();
   const int wave = wave_m * 2 + wk;
-  store_rows32<FN, BN>(a, keep, m_tile + wave_m * 64 + wk * 32, c_tile, lane, smem + (size_t)wave * out_stage_bytes(BN));
+  store_rows32<FN, BN>(a, keep, m_tile + wave_m * 64 + wk * 32, c_tile, lane, smem + (size_t)wave * out_stage_bytes(BN),
+                       smem + (size_t)4 * out_stage_bytes(BN));
 }
 
 // The wide-channel kernel (conv_wide_kernels.hip): input channels a multiple of 64.

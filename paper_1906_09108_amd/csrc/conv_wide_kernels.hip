@@ -47,7 +47,7 @@ __global__ __launch_bounds__(256) void conv_gather_dma_kernel(GatherConvArgs a, 
   constexpr int NJ = JX + JW;
   constexpr int FM = 2, FN = BN / 32;
   static_assert((STAGES - 2) * NJ < 64, "vmcnt range");
-  static_assert((size_t)STAGES * R * ROWB >= (size_t)4 * FN * 16 * 256 && (size_t)STAGES * R * ROWB >= (size_t)4 * out_stage_bytes(BN), "room for the output stage");
+  static_assert((size_t)STAGES * R * ROWB >= (size_t)4 * FN * 16 * 256 && (size_t)STAGES * R * ROWB >= (size_t)4 * out_stage_bytes(BN) + stats_stage_bytes(BN), "room for the output stage");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // STAGES * R * ROWB
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -201,7 +201,7 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
   constexpr int LDS_BYTES = 2 * XBYTES + WS * WBYTES;
   static_assert((WS - 2) * JW + JX < 64, "vmcnt range");
   static_assert(WS >= 3 && WS <= 9, "pipeline depth");
-  static_assert((size_t)LDS_BYTES >= (size_t)4 * FN * 16 * 256 && (size_t)LDS_BYTES >= (size_t)4 * out_stage_bytes(BN), "room for the output stage");
+  static_assert((size_t)LDS_BYTES >= (size_t)4 * FN * 16 * 256 && (size_t)LDS_BYTES >= (size_t)4 * out_stage_bytes(BN) + stats_stage_bytes(BN), "room for the output stage");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // LDS_BYTES
 
   const int tid = threadIdx.x, lane = tid & 63;

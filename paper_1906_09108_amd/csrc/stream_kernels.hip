@@ -426,6 +426,7 @@ __global__ void avgpool_kernel(const bf16_t* __restrict__ o, float* __restrict__
   if (idx >= N * C) return;
   const int n = idx / C, c = idx % C;
   float s = 0.f;
+#pragma unroll 16
   for (int p = 0; p < HW; ++p) s += (float)o[((size_t)n * HW + p) * C + c];
   pooled[idx] = s / (float)HW;
 }
@@ -492,11 +493,13 @@ __global__ void fc_bwd_kernel(const float* __restrict__ pooled, const float* __r
   if (idx < J * C) {
     const int j = idx / C, c = idx % C;
     float s = 0.f;
-    for (int n = 0; n < N; ++n) s += dl[(size_t)n * J + j] * pooled[(size_t)n * C + c];
+#pragma unroll 16
+    for (int n = 0; n < N; ++n) s += dl[(size_t)n * J + j] * pooled[(size_t)n * C + c];   // loads of 16 rows in flight; the sum stays in order
     dW[idx] = s;
   }
   if (idx < J) {
     float s = 0.f;
+#pragma unroll 16
     for (int n = 0; n < N; ++n) s += dl[(size_t)n * J + idx];
     db[idx] = s;
   }
