@@ -1238,6 +1238,15 @@ __global__ __launch_bounds__(256) void conv_wgrad_tall_kernel(WgradArgs a, Wgrad
     acc[K / FB][K % FB] = mfma32(frag(set_tag, K / FB), frag(set_tag, FA + K % FB), acc[K / FB][K % FB]);
   };
 
+  auto settle = [&](auto set_tag) {   // every fragment of the set has landed
+    constexpr int S = decltype(set_tag)::value;
+    static_for<NF>([&](auto f_tag) {
+      constexpr int F = decltype(f_tag)::value;
+      v4s16 &l0 = flo[S][F], &h0 = fhi[S][F];
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(l0), "+v"(h0));
+    });
+  };
+
   // prologue: chunks 0 .. STAGES-2 in flight, chunk 0 visible, its fragments in set 0
 #pragma unroll
   for (int p = 0; p < STAGES - 1; ++p)
@@ -1261,28 +1270,29 @@ __global__ __launch_bounds__(256) void conv_wgrad_tall_kernel(WgradArgs a, Wgrad
   // One chunk = NM (MFMA, piece) slots on one fragment set.  After slot 1: barrier c+1 (chunk c+1 visible,
   // everybody done reading chunk c-1).  Slots 2 .. NF+1: the reads of chunk c+1 into the other set, two per
   // slot.  Slots 2 ..: the NJ loads of chunk c+STAGES-1 into the stage of chunk c-1, one per slot.
-  // Whether a next chunk exists and whether there is still something to load are run-time (wave-uniform)
-  // conditions, and the fragment set alternates at compile time (the loop below takes chunks in pairs): a
-  // run-time choice of the set makes the compiler shuffle all accumulators between the two variants.
+  // Whether a next chunk exists and whether there is still something to load are compile-time tags (a taken
+  // branch costs the single wave of a SIMD more than an MFMA lasts), and the fragment set alternates at compile
+  // time too (the loops below take chunks in pairs): a run-time choice of the set makes the compiler shuffle
+  // all accumulators between the two variants.
   static_assert(NF + 2 <= NM && NJ + 2 <= NM, "slots of a chunk");
-  auto step = [&](auto set_tag, int c) {
+  auto step = [&](auto set_tag, int c, auto next_tag, auto issue_tag) {
     constexpr int S = decltype(set_tag)::value;
     using other = std::integral_constant<int, 1 - S>;
-    const bool next = c + 1 < n, issue = c + STAGES - 1 < n;
+    constexpr bool next = decltype(next_tag)::value, issue = decltype(issue_tag)::value;
     static_for<NM>([&](auto k) {
       constexpr int K = decltype(k)::value;
       if constexpr (K < FB || K % FB == 0) {
-        // reads of the other set issued meanwhile: two per slot from slot 2 on (only when there is a next chunk;
-        // without one fewer are outstanding and the bound below is merely not tight)
+        // reads of the other set issued meanwhile: two per slot from slot 2 on (with no next chunk everything
+        // is waited for at slot 2 instead)
         constexpr int NEWER = K > 2 ? 2 * ((K - 2) < NF ? (K - 2) : NF) : 0;
         before_mma(set_tag, k, std::integral_constant<int, 2 * (NF - needed(K)) + NEWER>{});
       }
       mma_one(set_tag, k);
-      if (next) {
+      if constexpr (next) {
         if constexpr (K == 1) {
           // chunk c+1 has landed when only the chunks issued after it are outstanding; once nothing is issued
           // any more, simply wait for everything
-          if (issue) wait_vmcnt<(STAGES - 3) * NJ>(); else wait_vmcnt<0>();
+          if constexpr (issue) wait_vmcnt<(STAGES - 3) * NJ>(); else wait_vmcnt<0>();
           asm volatile("" ::: "memory");
           __builtin_amdgcn_s_barrier();
           asm volatile("" ::: "memory");
@@ -1291,21 +1301,39 @@ __global__ __launch_bounds__(256) void conv_wgrad_tall_kernel(WgradArgs a, Wgrad
           read_one(other{}, std::integral_constant<int, 2 * (K - 2)>{}, c + 1);
           read_one(other{}, std::integral_constant<int, 2 * (K - 2) + 1>{}, c + 1);
         }
+      } else {
+        if constexpr (K == 2) settle(set_tag);
       }
       if constexpr (K >= 2 && K - 2 < NJ) {
-        if (issue) issue_one(K - 2, c + STAGES - 1);
+        if constexpr (issue) issue_one(K - 2, c + STAGES - 1);
       }
       __builtin_amdgcn_sched_barrier(0);
     });
-    if (issue) issue_done();
+    if constexpr (issue) issue_done();
   };
   {
+    using yes = std::true_type;
+    using no = std::false_type;
     int c = 0;
-    for (; c + 1 < n; c += 2) {
-      step(set0{}, c);
-      step(set1{}, c + 1);
+    for (; c + STAGES < n; c += 2) {        // both chunks of the pair still load
+      step(set0{}, c, yes{}, yes{});
+      step(set1{}, c + 1, yes{}, yes{});
     }
-    if (c < n) step(set0{}, c);
+    if (c + STAGES - 1 < n) {               // one more chunk to load: a mixed pair (n >= STAGES >= 4: c + 1 < n - 1)
+      step(set0{}, c, yes{}, yes{});
+      step(set1{}, c + 1, yes{}, no{});
+      c += 2;
+    }
+    for (; c + 2 < n; c += 2) {
+      step(set0{}, c, yes{}, no{});
+      step(set1{}, c + 1, yes{}, no{});
+    }
+    if (c + 2 == n) {
+      step(set0{}, c, yes{}, no{});
+      step(set1{}, c + 1, no{}, no{});
+    } else if (c < n) {
+      step(set0{}, c, no{}, no{});
+    }
   }
 
   // ---- add the two pixel halves: wave (wave_m, wk) keeps input-channel block wk of its two and receives its
