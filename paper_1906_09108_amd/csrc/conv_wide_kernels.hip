@@ -27,6 +27,14 @@ __device__ __forceinline__ void dma16(const void* gsrc, void* lds_wave_base) {
                                    (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
 }
 
+// Workgroups are dealt to the 8 XCDs round robin (XCD = block index mod 8).  This is the inverse numbering: the
+// blocks that run on one XCD get consecutive logical indices (any grid size), so that neighbours in the logical
+// order share an L2.
+__device__ __forceinline__ int xcd_consecutive(int block, int total) {
+  const int base = total >> 3, rem = total & 7, x = block & 7, q = block >> 3;
+  return x * base + (x < rem ? x : rem) + q;
+}
+
 // s_waitcnt vmcnt(n) only (expcnt and lgkmcnt left at "no wait")
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
@@ -782,13 +790,15 @@ __global__ __launch_bounds__(256) void conv_wgrad128_kernel(WgradArgs a, Wgrad12
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wave_m = wave & 1, wk = wave >> 1;
 
-  int t = blockIdx.x;
-  const int total = gridDim.x;
-  if ((total & 7) == 0) t = (blockIdx.x & 7) * (total >> 3) + (blockIdx.x >> 3);
+  // Every block streams its channels of both operands over all its pixels, and what an XCD's blocks have in
+  // common is fetched once into its L2.  So the blocks of an XCD are consecutive in the order (split, output
+  // tile, input tile, tap): one pixel split (or two), few channel tiles, all their taps.  Dealt round robin,
+  // every XCD would fetch both operands in full: 8 x 21 MB per launch.
+  int t = xcd_consecutive(blockIdx.x, gridDim.x);
+  const int tapi = t % a.ntaps; t /= a.ntaps;
   const int ci_t = t % L.ci_tiles; t /= L.ci_tiles;
-  const int co_t = t % L.co_tiles; t /= L.co_tiles;
-  const int tapi = t % a.ntaps;
-  const int split = t / a.ntaps;
+  const int co_t = t % L.co_tiles;
+  const int split = t / L.co_tiles;
   const int co0 = co_t * BC, ci0 = ci_t * BC;
   const int tp = a.tap[tapi];
   const int dh = (tp & 0xff) - 8, dw = ((tp >> 8) & 0xff) - 8;
@@ -1114,13 +1124,12 @@ __global__ __launch_bounds__(256) void conv_wgrad_tall_kernel(WgradArgs a, Wgrad
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wave_m = wave & 1, wk = wave >> 1;
 
-  int t = blockIdx.x;
-  const int total = gridDim.x;
-  if ((total & 7) == 0) t = (blockIdx.x & 7) * (total >> 3) + (blockIdx.x >> 3);
+  // blocks of one XCD: consecutive in the order (split, output tile, input tile, tap), see the 128 x 128 kernel
+  int t = xcd_consecutive(blockIdx.x, gridDim.x);
+  const int tapi = t % a.ntaps; t /= a.ntaps;
   const int ci_t = t % L.ci_tiles; t /= L.ci_tiles;
-  const int co_t = t % L.co_tiles; t /= L.co_tiles;
-  const int tapi = t % a.ntaps;
-  const int split = t / a.ntaps;
+  const int co_t = t % L.co_tiles;
+  const int split = t / L.co_tiles;
   const int co0 = co_t * TA, ci0 = ci_t * TB;
   const int tp = a.tap[tapi];
   const int dh = (tp & 0xff) - 8, dw = ((tp >> 8) & 0xff) - 8;
