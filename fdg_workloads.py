@@ -279,3 +279,54 @@ def conv_flops(spec: ModuleSpec) -> int:
         first = False
         c, h, w = L.c_out, ho, wo
     return total
+
+
+# ------------------------------------------------------------------------------------------------
+# A small network cut into K modules (for the K-module driver), and separable synthetic data
+# ------------------------------------------------------------------------------------------------
+def chain_specs(K: int, n: int = 16, width: int = 16, hw: int = 8, blocks: int = 1, beta: float = 0.5,
+                num_classes: int = 10, lr: float = 0.05, weight_decay: float = 5e-4, momentum: float = 0.9) -> List[ModuleSpec]:
+    """K module descriptions of a post-activation ResNet: stem 3 -> width, K * blocks basic blocks (the first block of
+    the upper half doubles the width with stride 2 when K > 1), average pool + FC + softmax cross-entropy.  Module k
+    (0 = input side) holds blocks [k * blocks, (k+1) * blocks); the stem goes to module 0 and the head to module
+    K-1.  Delays are the 2(K-1-k) of Fig. 1(a); beta is given to every module except the last (Section III-B)."""
+    layers: List[List[Layer]] = [[] for _ in range(K)]
+    layers[0].append(Layer(STEM, 3, width, 1))
+    c = width
+    for k in range(K):
+        for b in range(blocks):
+            if K > 1 and k == (K + 1) // 2 and b == 0:
+                layers[k].append(Layer(BASIC_POSTACT, c, 2 * c, 2))
+                c = 2 * c
+            else:
+                layers[k].append(Layer(BASIC_POSTACT, c, c, 1))
+    layers[K - 1].append(Layer(HEAD_POSTACT, c))
+    specs = []
+    cin, h = 3, hw
+    for k in range(K):
+        sp = ModuleSpec(n=n, c_in=cin, h_in=h, w_in=h, layers=layers[k], delay=2 * (K - 1 - k), is_bottom=(k == 0),
+                        num_classes=num_classes, beta=(1.0 if k == K - 1 else beta), momentum=momentum,
+                        weight_decay=weight_decay, lr=lr, name="chain%d_module%d" % (K, k))
+        specs.append(sp)
+        if not sp.is_top:
+            _, cin, h, _ = sp.output_shape()
+    return specs
+
+
+def whole_network_spec(specs: Sequence[ModuleSpec]) -> ModuleSpec:
+    """The same layers as one module (delay 0, no shrinking): the network the chain was cut from.  Its flat
+    parameter vector is the concatenation of the modules' vectors."""
+    layers = [L for sp in specs for L in sp.layers]
+    s0 = specs[0]
+    return ModuleSpec(n=s0.n, c_in=s0.c_in, h_in=s0.h_in, w_in=s0.w_in, layers=layers, delay=0, is_bottom=True,
+                      num_classes=s0.num_classes, beta=1.0, momentum=s0.momentum, weight_decay=s0.weight_decay,
+                      lr=s0.lr, name="whole_network")
+
+
+def make_separable_batch(spec: ModuleSpec, step: int, seed: int = 0, noise: float = 0.5):
+    """(x, labels) of a classification task a small network learns within tens of iterations: every class has a
+    fixed random prototype image (seeded), a sample is its class prototype plus N(0, noise^2)."""
+    protos = normal(seed, 900, (spec.num_classes, spec.c_in, spec.h_in, spec.w_in))
+    labels = _rng(seed, 901 + 2 * step).integers(0, spec.num_classes, size=spec.n).astype(np.int32)
+    x = protos[labels] + noise * normal(seed, 902 + 2 * step, (spec.n, spec.c_in, spec.h_in, spec.w_in))
+    return x.astype(np.float32), labels

@@ -41,9 +41,16 @@ moves a per-channel sum by a whole term, which alone puts parameter gradients se
 Taking the decision in the kernel's storage precision on both sides removes that, and what remains
 is the arithmetic.
 
+OracleChain runs K such workers as Algorithm I does: every iteration each module back-propagates the
+oldest saved batch with the gradient it received, updates, forwards the input it received, and the
+tensors are exchanged "right before the iteration ends" (Section III-A, "communication"; Fig. 1(a)).
+
 Parity status: every function of this oracle is pinned by tests/test_oracle_*.py (finite
 differences in float64, torch-CPU autograd as an independent library, closed forms, adjoint
-identities, brute force, and the paper's own K=3 delay example).  Nothing here is "parity unpinned".
+identities, brute force, and the paper's own K=3 delay example; the chain against the integer
+schedule, against one module on the whole network for K = 1, against autograd of the composed
+network for the stale gradient of Eq. 13, and against Eq. 16/17 for the compounded shrinking).
+Nothing here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -558,3 +565,79 @@ def fdg_schedule(K: int, T: int):
         for k in range(0, K + 1):
             inbox_grad[k] = send_grad.get(k)
     return fwd, bwd, depth
+
+
+# ------------------------------------------------------------------------------------------------
+# K modules run as Algorithm I
+# ------------------------------------------------------------------------------------------------
+class OracleChain:
+    """K module workers and their mailboxes (Section III-A; Algorithm I).  `specs[k]`, k = 0..K-1 from
+    the input side, describe the modules: the first is a bottom module, the last ends in the loss, the
+    output shape of each is the input shape of the next, and module k can hold the 2(K-1-k) saved
+    forwards that are waiting for their gradients plus the newest one (Fig. 1(a): the gradient of
+    module k -- k counted from 1 there -- is 2(K-k) iterations late), i.e. specs[k].delay >= 2(K-1-k).
+
+    One call of step() is one iteration t = 1, 2, ...: batch t enters module 0.  Per module, in the
+    order of Algorithm I: (1) if a gradient was received at the end of the previous iteration,
+    delayed backward (shrunk by that module's beta) and update; (2) if an input was received, forward;
+    (3) what was produced is delivered at the end of the iteration.  The last module has delay 0:
+    it forwards its input, takes the loss gradient of that same batch, back-propagates and updates
+    (Section III-B: its gradient is not shrunk).  Until the first tensors arrive a module idles, which
+    is the max{0, .} clamp of the batch indices in Section IV."""
+
+    def __init__(self, specs, dtype=np.float32, storage: str = "fp32"):
+        K = len(specs)
+        assert K >= 1
+        self.K = K
+        self.mods = [OracleModule(sp, dtype, storage) for sp in specs]
+        assert self.mods[-1].is_top and all(not m.is_top for m in self.mods[:-1])
+        for k, sp in enumerate(specs):
+            assert sp.delay >= 2 * (K - 1 - k), "module %d needs a history of %d forwards" % (k, 2 * (K - 1 - k))
+            assert bool(sp.is_bottom) == (k == 0)
+        self.t = 0
+        self.inbox_act: List[Optional[tuple]] = [None] * K    # (batch, tensor) waiting at module k's input
+        self.inbox_grad: List[Optional[tuple]] = [None] * K   # (batch, tensor) waiting at module k's output
+        self.labels: Dict[int, np.ndarray] = {}
+        self.fwd_batch = [0] * K      # what each module did in the last iteration (0 = idle)
+        self.bwd_batch = [0] * K
+
+    def step(self, x, labels, lr: float):
+        """One iteration.  Returns (batch, loss, logits) of the batch the last module saw, or None
+        while it is still idle."""
+        K = self.K
+        self.t += 1
+        t = self.t
+        self.labels[t] = np.asarray(labels)
+        send_act: Dict[int, tuple] = {}
+        send_grad: Dict[int, tuple] = {}
+        self.fwd_batch, self.bwd_batch = [0] * K, [0] * K
+        result = None
+        for k, m in enumerate(self.mods):
+            inp = (t, x) if k == 0 else self.inbox_act[k]
+            if k == K - 1:
+                if inp is not None:
+                    b, z = inp
+                    out = m.forward(z, self.labels.pop(b))
+                    result = (b, float(out.ravel()[0]), np.array(out.ravel()[1:]).reshape(m.spec.n, -1))
+                    gin = m.backward_delayed(None)
+                    m.update(lr)
+                    self.fwd_batch[k] = self.bwd_batch[k] = b
+                    if k > 0:
+                        send_grad[k - 1] = (b, gin)
+            else:
+                got = self.inbox_grad[k]
+                if got is not None:
+                    b, g = got
+                    gin = m.backward_delayed(g)
+                    m.update(lr)
+                    self.bwd_batch[k] = b
+                    if k > 0:
+                        send_grad[k - 1] = (b, gin)
+                if inp is not None:
+                    b, z = inp
+                    send_act[k + 1] = (b, m.forward(z))
+                    self.fwd_batch[k] = b
+        # communication, right before the iteration ends
+        self.inbox_act = [send_act.get(k) for k in range(K)]
+        self.inbox_grad = [send_grad.get(k) for k in range(K)]
+        return result
