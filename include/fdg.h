@@ -154,6 +154,13 @@ fdg_status fdg_get_bn_running(const fdg_module* m, float* host_dst, size_t count
 /* Shape of the forward's y: out[0..3] = n, c, h, w (top module: 1, 1, 1, 1 + n*num_classes). */
 fdg_status fdg_output_shape(const fdg_module* m, int32_t out[4]);
 
+/* Shape of the forward's x: out[0..3] = n, c_in, h_in, w_in. */
+fdg_status fdg_input_shape(const fdg_module* m, int32_t out[4]);
+
+/* What the module was created as: the ring depth `delay`, whether it is a bottom module (no input
+ * gradient) and whether it is a top module (ends in the loss).  Any output pointer may be NULL.   */
+fdg_status fdg_module_traits(const fdg_module* m, int32_t* delay, int32_t* is_bottom, int32_t* is_top);
+
 /* Ring state: number of outstanding contexts and the sequence numbers (0-based count of forwards)
  * of the oldest and newest one (-1 when empty).  Any of the three output pointers may be NULL.
  * A forward with sequence number s is stored in ring slot s mod (delay+1).                       */

@@ -1,8 +1,8 @@
 """MI355X-native FDG module worker (arXiv 1906.09108): thin Python binding over the C-ABI library
 libfdg.so.  Importing the package does not load the library; `binding.load()` does and fails loudly
 when it has not been built."""
-from .binding import (FdgError, FdgModule, fdg_backward_delayed, fdg_destroy, fdg_forward, fdg_module_create,
+from .binding import (FdgChain, FdgError, FdgModule, fdg_backward_delayed, fdg_destroy, fdg_forward, fdg_module_create,
                       fdg_module_workspace_bytes, fdg_update, load)
 
-__all__ = ["FdgError", "FdgModule", "load", "fdg_module_workspace_bytes", "fdg_module_create", "fdg_forward",
+__all__ = ["FdgChain", "FdgError", "FdgModule", "load", "fdg_module_workspace_bytes", "fdg_module_create", "fdg_forward",
            "fdg_backward_delayed", "fdg_update", "fdg_destroy"]

@@ -1,6 +1,6 @@
 """Argument marshalling between Python and libfdg.so.  No arithmetic happens here: torch only owns
 device memory and streams; every step of the module's forward, delayed backward and update runs in
-the library's kernels.  Function names and argument order follow include/fdg.h."""
+the library's kernels.  Function names and argument order follow include/fdg.h and include/fdg_chain.h."""
 from __future__ import annotations
 
 import ctypes
@@ -46,7 +46,8 @@ _lib: Optional[ctypes.CDLL] = None
 EXPORTS = ["fdg_module_workspace_bytes", "fdg_module_create", "fdg_forward", "fdg_backward_delayed", "fdg_update",
            "fdg_destroy", "fdg_param_count", "fdg_set_params", "fdg_get_params", "fdg_get_grads", "fdg_get_momentum",
            "fdg_bn_stat_count", "fdg_get_bn_running", "fdg_output_shape", "fdg_queue_state", "fdg_status_string",
-           "fdg_profile_enable", "fdg_profile_read"]
+           "fdg_profile_enable", "fdg_profile_read", "fdg_input_shape", "fdg_module_traits",
+           "fdg_chain_mailbox_bytes", "fdg_chain_create", "fdg_chain_step", "fdg_chain_state", "fdg_chain_destroy"]
 
 
 def load() -> ctypes.CDLL:
@@ -77,6 +78,15 @@ def load() -> ctypes.CDLL:
     lib.fdg_profile_enable.argtypes, lib.fdg_profile_enable.restype = [vp, i32], i32
     lib.fdg_profile_read.argtypes = [vp, ctypes.POINTER(fdg_profile_entry), i32, ctypes.POINTER(i32)]
     lib.fdg_profile_read.restype = i32
+    lib.fdg_input_shape.argtypes, lib.fdg_input_shape.restype = [vp, ctypes.POINTER(i32 * 4)], i32
+    lib.fdg_module_traits.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    lib.fdg_module_traits.restype = i32
+    lib.fdg_chain_mailbox_bytes.argtypes, lib.fdg_chain_mailbox_bytes.restype = [ctypes.POINTER(vp), i32], sz
+    lib.fdg_chain_create.argtypes, lib.fdg_chain_create.restype = [ctypes.POINTER(vp), i32, vp, sz, ctypes.POINTER(vp)], i32
+    lib.fdg_chain_step.argtypes, lib.fdg_chain_step.restype = [vp, vp, vp, f32, vp, ctypes.POINTER(i32), vp], i32
+    lib.fdg_chain_state.argtypes = [vp, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    lib.fdg_chain_state.restype = i32
+    lib.fdg_chain_destroy.argtypes, lib.fdg_chain_destroy.restype = [vp], None
     _lib = lib
     return lib
 
@@ -255,3 +265,59 @@ class FdgModule:
         o, a, b = ctypes.c_int32(), ctypes.c_int64(), ctypes.c_int64()
         load().fdg_queue_state(self.handle, ctypes.byref(o), ctypes.byref(a), ctypes.byref(b))
         return int(o.value), int(a.value), int(b.value)
+
+
+class FdgChain:
+    """K modules run as Algorithm I (include/fdg_chain.h).  Owns the modules' workspaces, the mailbox memory and
+    the chain handle; step() is one C call."""
+
+    def __init__(self, specs: Sequence, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.device = torch.device(device)
+        self.modules = [FdgModule(sp, device) for sp in specs]
+        self.K = len(self.modules)
+        self._handles = (ctypes.c_void_p * self.K)(*[m.handle for m in self.modules])
+        nbytes = int(load().fdg_chain_mailbox_bytes(self._handles, self.K))
+        if nbytes == 0 and self.K > 1:
+            raise FdgError(FDG_ERR_INVALID_ARG, "fdg_chain_mailbox_bytes")
+        self.mailbox = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+        off = (-self.mailbox.data_ptr()) % 256
+        self._mb_view = self.mailbox[off:off + max(nbytes, 1)]
+        out = ctypes.c_void_p()
+        st = load().fdg_chain_create(self._handles, self.K, _ptr(self._mb_view), nbytes, ctypes.byref(out))
+        if st != FDG_OK:
+            raise FdgError(st, "fdg_chain_create")
+        self.handle = out.value
+        top = self.modules[-1]
+        self.top_y = top.new_output()
+
+    def step(self, x, labels, lr: float, stream=None) -> int:
+        """One iteration on batch (x, labels), both CUDA tensors.  Returns the 1-based batch whose loss and logits
+        are now being written to self.top_y (0 while the last module idles)."""
+        b = ctypes.c_int32()
+        st = load().fdg_chain_step(self.handle, _ptr(x), _ptr(labels), float(lr), _ptr(self.top_y), ctypes.byref(b),
+                                   _stream_handle(stream))
+        if st != FDG_OK:
+            raise FdgError(st, "fdg_chain_step")
+        return int(b.value)
+
+    def state(self) -> Tuple[int, list, list]:
+        t = ctypes.c_int64()
+        f, b = (ctypes.c_int32 * self.K)(), (ctypes.c_int32 * self.K)()
+        load().fdg_chain_state(self.handle, ctypes.byref(t), f, b)
+        return int(t.value), list(f), list(b)
+
+    def close(self):
+        if getattr(self, "handle", None):
+            self.torch.cuda.synchronize(self.device)
+            load().fdg_chain_destroy(self.handle)
+            self.handle = None
+        for m in getattr(self, "modules", []):
+            m.close()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

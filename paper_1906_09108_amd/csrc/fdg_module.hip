@@ -793,6 +793,20 @@ fdg_status fdg_output_shape(const fdg_module* m, int32_t out[4]) {
   return FDG_OK;
 }
 
+fdg_status fdg_input_shape(const fdg_module* m, int32_t out[4]) {
+  if (!m || !out) return FDG_ERR_INVALID_ARG;
+  out[0] = m->p.d.n; out[1] = m->p.d.c_in; out[2] = m->p.d.h_in; out[3] = m->p.d.w_in;
+  return FDG_OK;
+}
+
+fdg_status fdg_module_traits(const fdg_module* m, int32_t* delay, int32_t* is_bottom, int32_t* is_top) {
+  if (!m) return FDG_ERR_INVALID_ARG;
+  if (delay) *delay = m->p.d.delay;
+  if (is_bottom) *is_bottom = m->p.d.is_bottom ? 1 : 0;
+  if (is_top) *is_top = m->p.is_top ? 1 : 0;
+  return FDG_OK;
+}
+
 fdg_status fdg_queue_state(const fdg_module* m, int32_t* outstanding, int64_t* oldest_seq, int64_t* newest_seq) {
   if (!m) return FDG_ERR_INVALID_ARG;
   const int64_t n = m->seq_fwd - m->seq_bwd;

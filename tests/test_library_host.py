@@ -22,7 +22,7 @@ def _declared(header, prefix):
 def test_library_exports_every_declared_symbol():
     from paper_1906_09108_amd import kernels
     lib = binding.load()
-    names = _declared("fdg.h", "fdg_")
+    names = sorted(set(_declared("fdg.h", "fdg_") + _declared("fdg_chain.h", "fdg_chain_")))
     assert set(names) == set(binding.EXPORTS)
     knames = _declared("fdg_kernels.h", "fdgk_")
     assert set(knames) == set(kernels.KERNEL_EXPORTS)
@@ -65,3 +65,17 @@ def test_invalid_descriptors_are_rejected():
     assert lib.fdg_forward(None, None, None, None, None) == binding.FDG_ERR_INVALID_ARG
     assert lib.fdg_update(None, 0.1, None) == binding.FDG_ERR_INVALID_ARG
     lib.fdg_destroy(None)
+
+
+def test_chain_rejects_bad_arguments_without_a_gpu():
+    """No module can be created here (no device memory), so only the argument checks that come first."""
+    lib = binding.load()
+    assert lib.fdg_chain_mailbox_bytes(None, 2) == 0
+    arr = (ctypes.c_void_p * 2)(None, None)
+    assert lib.fdg_chain_mailbox_bytes(arr, 2) == 0
+    out = ctypes.c_void_p()
+    assert lib.fdg_chain_create(arr, 2, None, 0, ctypes.byref(out)) == binding.FDG_ERR_INVALID_ARG
+    assert lib.fdg_chain_create(arr, 0, None, 0, ctypes.byref(out)) == binding.FDG_ERR_INVALID_ARG
+    assert lib.fdg_chain_step(None, None, None, 0.1, None, None, None) == binding.FDG_ERR_INVALID_ARG
+    assert lib.fdg_chain_state(None, None, None, None) == binding.FDG_ERR_INVALID_ARG
+    lib.fdg_chain_destroy(None)
