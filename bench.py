@@ -41,6 +41,9 @@ def parse_args():
                     help="first run 3 plain device copies of 1 GiB (float32): the known traffic a profiler's HBM counters "
                          "are scaled by")
     ap.add_argument("--cpu-sample-batch", type=int, default=0, help="batch of the oracle sample (0 = pick by config)")
+    ap.add_argument("--chain", type=int, default=0, metavar="K",
+                    help="instead of the module step: time one iteration of Algorithm I for the whole WRN-28-10 cut "
+                         "into K modules that share this GPU (one stream each); prints its own JSON line")
     return ap.parse_args()
 
 
@@ -64,12 +67,58 @@ def cpu_baseline(idx: int, sample_batch: int):
             "sample": f"same layers at batch {n} (of {W.config(idx).n}), 1 step forward+backward+update, {dt:.1f} s"}
 
 
+def chain_bench(args):
+    """Whole-network iteration of Algorithm I, K modules on K streams of this one GPU (the paper runs them on K
+    GPUs).  Not the headline metric: a second, reported figure."""
+    import torch
+    import fdg_workloads as W
+    from paper_1906_09108_amd import FdgChain
+    specs = W.wrn_28_10_chain(args.chain)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    chain = FdgChain(specs, dev)
+    for k, m in enumerate(chain.modules):
+        m.set_params(W.make_params(specs[k], k))
+    pool = 4
+    xs = [torch.from_numpy(W.make_input(specs[0], t)).to(dev) for t in range(pool)]
+    labels = [torch.from_numpy(W.make_labels(specs[-1], t)).to(dev) for t in range(pool)]
+    lr = 0.01
+    warm = max(args.warmup, 2 * args.chain)            # every module's history is in steady state after 2K iterations
+    for i in range(warm):
+        chain.step(xs[i % pool], labels[i % pool], lr)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        chain.step(xs[(warm + i) % pool], labels[(warm + i) % pool], lr)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    loss = float(chain.top_y[0].item())
+    flops = sum(W.conv_flops(sp) for sp in specs)
+    chain.close()
+    if not (loss == loss and abs(loss) < 1e30):
+        print("non-finite loss", file=sys.stderr)
+        sys.exit(1)
+    print(json.dumps({
+        "metric": "images/sec, one iteration of Algorithm I over all K modules (whole network) on one GPU",
+        "value": specs[0].n * args.steps / elapsed, "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": warm,
+        "ms_per_step": 1e3 * elapsed / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "WRN-28-10, K=%d modules sharing one GPU" % args.chain, "batch": specs[0].n,
+                   "delays": [sp.delay for sp in specs], "params": sum(W.param_count(sp) for sp in specs),
+                   "useful_conv_gflop_per_step": flops / 1e9},
+        "step_tflops": flops / (elapsed / args.steps) / 1e12,
+        "paper_context": "FDG K=2 WRN-28-10: 354.56 images/s on 2x 1080Ti, BP 188.16 on 1x (Table VII); other hardware",
+    }))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py measures one module worker on ONE GPU; this build has no multi-GPU path "
               f"(got --gpus {args.gpus}). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
+    if args.chain:
+        return chain_bench(args)
     import numpy as np
     import torch
     import fdg_workloads as W

@@ -330,3 +330,30 @@ def make_separable_batch(spec: ModuleSpec, step: int, seed: int = 0, noise: floa
     labels = _rng(seed, 901 + 2 * step).integers(0, spec.num_classes, size=spec.n).astype(np.int32)
     x = protos[labels] + noise * normal(seed, 902 + 2 * step, (spec.n, spec.c_in, spec.h_in, spec.w_in))
     return x.astype(np.float32), labels
+
+
+def wrn_28_10_chain(K: int = 2, n: int = 128, beta: float = 0.7) -> List[ModuleSpec]:
+    """The whole WRN-28-10 of the paper's Table VII cut "evenly" into K modules of 12 / K pre-activation blocks
+    (K in 1, 2, 3, 4, 6): stem 3 -> 16, 4 blocks of 160 channels at 32x32, 4 of 320 at 16x16, 4 of 640 at 8x8,
+    BN/ReLU/average pool/FC.  The stem is this build's conv + BN + ReLU layer (the original has a bare
+    convolution there).  Delays 2(K-1-k) as in Fig. 1(a); beta on every module but the last."""
+    assert 12 % K == 0
+    blocks: List[Layer] = []
+    c = 16
+    for width, stride in ((160, 1), (320, 2), (640, 2)):
+        for b in range(4):
+            blocks.append(Layer(BASIC_PREACT, c, width, stride if b == 0 else 1))
+            c = width
+    per = 12 // K
+    hyper = dict(momentum=0.9, weight_decay=5e-4, bn_eps=1e-5, bn_momentum=0.1, lr=0.1)
+    specs = []
+    cin, h = 3, 32
+    for k in range(K):
+        ls = ([Layer(STEM, 3, 16, 1)] if k == 0 else []) + blocks[k * per:(k + 1) * per] \
+            + ([Layer(HEAD_PREACT, 640)] if k == K - 1 else [])
+        sp = ModuleSpec(n, cin, h, h, ls, delay=2 * (K - 1 - k), is_bottom=(k == 0), num_classes=10,
+                        beta=(1.0 if k == K - 1 else beta), name="WRN-28-10 K=%d module %d" % (K, k), **hyper)
+        specs.append(sp)
+        if not sp.is_top:
+            _, cin, h, _ = sp.output_shape()
+    return specs
