@@ -421,17 +421,39 @@ hipError_t launch_nhwc_to_nchw(const float* src, float* dst, int N, int C, int H
 }
 
 // ---- head -------------------------------------------------------------------------------------------
-__global__ void avgpool_kernel(const bf16_t* __restrict__ o, float* __restrict__ pooled, int N, int HW, int C) {
-  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= N * C) return;
-  const int n = idx / C, c = idx % C;
-  float s = 0.f;
-#pragma unroll 16
-  for (int p = 0; p < HW; ++p) s += (float)o[((size_t)n * HW + p) * C + c];
-  pooled[idx] = s / (float)HW;
+// pooled[n, c] = mean over the HW pixels of o[n, :, c].  One block per image and 256 channels: 32 groups of 8
+// channels (one 16-byte load per pixel) x 8 pixel phases, so that every thread has only HW/8 independent loads
+// and the eight partial sums of a channel are added, in a fixed order, through LDS.
+__global__ __launch_bounds__(256) void avgpool_kernel(const bf16_t* __restrict__ o, float* __restrict__ pooled, int N, int HW, int C) {
+  __shared__ float part[8][256 + 8];
+  const int n = blockIdx.y, c0 = blockIdx.x * 256;
+  const int cg = threadIdx.x & 31, ph = threadIdx.x >> 5;
+  const int c = c0 + cg * 8;
+  float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (c < C) {   // C % 8 == 0
+    const bf16_t* src = o + (size_t)n * HW * C + c;
+#pragma unroll 8
+    for (int p = ph; p < HW; p += 8) {
+      float f[8];
+      unpack8(*reinterpret_cast<const uint4*>(src + (size_t)p * C), f);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) s[i] += f[i];
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) part[ph][cg * 8 + i] = s[i];
+  __syncthreads();
+  const int cc = c0 + threadIdx.x;
+  if (cc < C) {
+    float t = 0.f;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) t += part[q][threadIdx.x];
+    pooled[(size_t)n * C + cc] = t / (float)HW;
+  }
 }
 hipError_t launch_avgpool(const bf16_t* o, float* pooled, int N, int HW, int C, hipStream_t s) {
-  hipLaunchKernelGGL(avgpool_kernel, dim3((N * C + 255) / 256), dim3(256), 0, s, o, pooled, N, HW, C);
+  if (C % 8 != 0 || N <= 0 || N > 65535) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(avgpool_kernel, dim3((C + 255) / 256, N), dim3(256), 0, s, o, pooled, N, HW, C);
   return hipGetLastError();
 }
 
@@ -487,33 +509,46 @@ hipError_t launch_softmax_ce(const float* logits, const int32_t* labels, float* 
 }
 
 // dW[j,c] = sum_n dl[n,j] p[n,c];  db[j] = sum_n dl[n,j];  dp[n,c] = sum_j dl[n,j] W[j,c]
-__global__ void fc_bwd_kernel(const float* __restrict__ pooled, const float* __restrict__ W, const float* __restrict__ dl,
-                              float* __restrict__ dW, float* __restrict__ db, float* __restrict__ dp, int N, int C, int J) {
-  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx < J * C) {
-    const int j = idx / C, c = idx % C;
-    float s = 0.f;
-#pragma unroll 16
-    for (int n = 0; n < N; ++n) s += dl[(size_t)n * J + j] * pooled[(size_t)n * C + c];   // loads of 16 rows in flight; the sum stays in order
-    dW[idx] = s;
+// Blocks [0, dp_blocks): one thread per dp element (J terms).  The other blocks: one per class j and 64
+// channels; the batch is dealt to 4 thread groups so that a thread has N/4 independent loads, and the four
+// partial sums are added in a fixed order through LDS.  db[j] comes from the blocks of channel chunk 0.
+__global__ __launch_bounds__(256) void fc_bwd_kernel(const float* __restrict__ pooled, const float* __restrict__ W,
+                                                     const float* __restrict__ dl, float* __restrict__ dW, float* __restrict__ db,
+                                                     float* __restrict__ dp, int N, int C, int J, int dp_blocks) {
+  __shared__ float part[4][64];
+  __shared__ float bpart[4];
+  if ((int)blockIdx.x < dp_blocks) {
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx < N * C) {
+      const int n = idx / C, c = idx % C;
+      float s = 0.f;
+      for (int j = 0; j < J; ++j) s += dl[(size_t)n * J + j] * W[(size_t)j * C + c];
+      dp[idx] = s;
+    }
+    return;
   }
-  if (idx < J) {
-    float s = 0.f;
-#pragma unroll 16
-    for (int n = 0; n < N; ++n) s += dl[(size_t)n * J + idx];
-    db[idx] = s;
+  const int b = blockIdx.x - dp_blocks, chunks = (C + 63) / 64;
+  const int j = b / chunks, c = (b % chunks) * 64 + (threadIdx.x & 63), q = threadIdx.x >> 6;
+  float s = 0.f, sb = 0.f;
+  const bool cok = c < C;
+#pragma unroll 8
+  for (int n = q; n < N; n += 4) {
+    const float d = dl[(size_t)n * J + j];
+    sb += d;
+    if (cok) s += d * pooled[(size_t)n * C + c];
   }
-  if (idx < N * C) {
-    const int n = idx / C, c = idx % C;
-    float s = 0.f;
-    for (int j = 0; j < J; ++j) s += dl[(size_t)n * J + j] * W[(size_t)j * C + c];
-    dp[idx] = s;
+  part[q][threadIdx.x & 63] = s;
+  if ((threadIdx.x & 63) == 0) bpart[q] = sb;
+  __syncthreads();
+  if (q == 0) {
+    if (cok) dW[(size_t)j * C + c] = (part[0][threadIdx.x] + part[1][threadIdx.x]) + (part[2][threadIdx.x] + part[3][threadIdx.x]);
+    if (threadIdx.x == 0 && b % chunks == 0) db[j] = (bpart[0] + bpart[1]) + (bpart[2] + bpart[3]);
   }
 }
 hipError_t launch_fc_bwd(const float* pooled, const float* W, const float* dl, float* dW, float* db, float* dp,
                          int N, int C, int J, hipStream_t s) {
-  const int total = (N > J ? N : J) * C;
-  hipLaunchKernelGGL(fc_bwd_kernel, dim3((total + 255) / 256), dim3(256), 0, s, pooled, W, dl, dW, db, dp, N, C, J);
+  const int dp_blocks = (N * C + 255) / 256, w_blocks = J * ((C + 63) / 64);
+  hipLaunchKernelGGL(fc_bwd_kernel, dim3(dp_blocks + w_blocks), dim3(256), 0, s, pooled, W, dl, dW, db, dp, N, C, J, dp_blocks);
   return hipGetLastError();
 }
 
