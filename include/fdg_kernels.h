@@ -44,6 +44,18 @@ int fdgk_conv_dgrad(const void* dy_b16, const void* wt_b16, const float* addend_
                     float* dx_f32, void* dx_b16, int n, int h, int w, int ci, int co, int ksize, int stride,
                     void* hip_stream);
 
+/* The data gradient ending in the ReLU and the batch norm it back-propagates into next (Eq. 8 / Eq. 9 applied to
+ * conv o ReLU o BN): with gate_b16 = the ReLU's output and bnx_b16 = the batch norm's input, both [n,h,w,cip],
+ *   dx = gate > 0 ? (data gradient + addend) : 0,
+ *   gsums[i] += sum over pixels of bf16(dx[..,i]),  gsums[cip+i] += sum of bf16(dx[..,i]) * bnx[..,i]
+ * (gsums_f32 [2*cip], zero it first): the two reductions of the batch-norm backward, taken in the output stage of the
+ * convolution instead of a pass of their own.  Only the wide kernels do this: fdgk_conv_dgrad_gates says (1 / 0) whether
+ * a shape is covered, fdgk_conv_dgrad_gated returns hipErrorInvalidValue (1) where it is not.                       */
+int fdgk_conv_dgrad_gates(int n, int h, int w, int ci, int co, int ksize, int stride);
+int fdgk_conv_dgrad_gated(const void* dy_b16, const void* wt_b16, const float* addend_f32, const void* gate_b16,
+                          const void* bnx_b16, float* gsums_f32, float* dx_f32, void* dx_b16, int n, int h, int w, int ci,
+                          int co, int ksize, int stride, void* hip_stream);
+
 /* Weight gradient, the adjoint in w, into dw_f32 [co][ksize*ksize][ci]:
  *   dw[o,r,q,i] (+)= sum_{n,ho,wo} dy[n,ho,wo,o] * x[n, ho*s+r-p, wo*s+q-p, i].
  * overwrite == 0: the sum is ADDED to dw (zero it first for the plain gradient); overwrite != 0: dw is
@@ -72,6 +84,13 @@ int fdgk_bn_apply(const void* x_b16, const float* sums_f32, const float* gamma, 
 int fdgk_bn_bwd(const void* dy, int dy_is_f32, const void* mask_b16, const void* x_b16, const float* sums_f32,
                 const float* gamma, float* scratch_f32, const float* addend_f32, float* dx_f32, void* dx_b16,
                 float* dgamma, float* dbeta, int m, int c, float eps, void* hip_stream);
+
+/* The second half of fdgk_bn_bwd for a gradient g_b16 [m, c] that is already gated and whose sums
+ * gsums_f32 = [sum g, sum g*x] were left by fdgk_conv_dgrad_gated: dbeta = sum g, dgamma = (sum g*x - mean * sum g) / sqrt(var+eps),
+ * dx as in fdgk_bn_bwd.                                                                                */
+int fdgk_bn_bwd_gated(const void* g_b16, const void* x_b16, const float* sums_f32, const float* gamma,
+                      const float* gsums_f32, const float* addend_f32, float* dx_f32, void* dx_b16, float* dgamma,
+                      float* dbeta, int m, int c, float eps, void* hip_stream);
 
 /* Momentum SGD with coupled weight decay (Eq. 11 with the optimiser of Section V-A), count % 4 == 0:
  *   g' = g + wd*theta;  v = mu*v + g';  theta = theta - lr*v.                                       */

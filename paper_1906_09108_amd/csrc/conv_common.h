@@ -142,9 +142,10 @@ __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x
   typedef const u32x2 __attribute__((address_space(1))) * gcu2;
   typedef u32x2 __attribute__((address_space(1))) * gu2;
   uint64_t p_addend = (uint64_t)a.addend, p_mask = (uint64_t)a.addmask, p_f32 = (uint64_t)a.out_f32, p_b16 = (uint64_t)a.out_b16;
+  uint64_t p_gate = (uint64_t)a.gate, p_bnx = (uint64_t)a.bnx;
   int Co = a.Co;
   int want_stats = a.stats != nullptr;
-  asm volatile("" : "+v"(p_addend), "+v"(p_mask), "+v"(p_f32), "+v"(p_b16), "+v"(Co), "+v"(want_stats));
+  asm volatile("" : "+v"(p_addend), "+v"(p_mask), "+v"(p_f32), "+v"(p_b16), "+v"(Co), "+v"(want_stats), "+v"(p_gate), "+v"(p_bnx));
   {
     const int p = lane & 31, half = lane >> 5;
 #pragma unroll
@@ -180,7 +181,7 @@ __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x
     size_t o[G];
     f32x4 v[G];
     f32x4 ad[G];
-    u32x2 mk[G];
+    u32x2 mk[G], gt[G], bx[G];
 #pragma unroll
     for (int k = 0; k < G; ++k) {
       const int q = (it0 + k) * 64 + lane;
@@ -190,6 +191,14 @@ __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x
       ok[k] = pix >= 0 && c < Co;
       o[k] = ok[k] ? (size_t)pix * Co + c : 0;
       v[k] = *reinterpret_cast<const f32x4*>(lds + p * PITCH + un * 16);
+    }
+    if (p_gate) {
+#pragma unroll
+      for (int k = 0; k < G; ++k) gt[k] = *(gcu2)(p_gate + 2 * o[k]);
+    }
+    if (p_bnx) {
+#pragma unroll
+      for (int k = 0; k < G; ++k) bx[k] = *(gcu2)(p_bnx + 2 * o[k]);
     }
     if (p_addend) {
 #pragma unroll
@@ -210,6 +219,15 @@ __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x
         v[k] += ad[k];
       }
     }
+    if (p_gate) {
+#pragma unroll
+      for (int k = 0; k < G; ++k) {
+        if (!(bf16_lo(gt[k][0]) > 0.f)) v[k][0] = 0.f;
+        if (!(bf16_hi(gt[k][0]) > 0.f)) v[k][1] = 0.f;
+        if (!(bf16_lo(gt[k][1]) > 0.f)) v[k][2] = 0.f;
+        if (!(bf16_hi(gt[k][1]) > 0.f)) v[k][3] = 0.f;
+      }
+    }
 #pragma unroll
     for (int k = 0; k < G; ++k) {
       const u32x2 packed = {pack_bf16x2(v[k][0], v[k][1]), pack_bf16x2(v[k][2], v[k][3])};
@@ -220,7 +238,12 @@ __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x
           const float r0 = bf16_lo(packed[0]), r1 = bf16_hi(packed[0]), r2 = bf16_lo(packed[1]), r3 = bf16_hi(packed[1]);
           const int kk = (it0 + k) % PERIOD;
           s1[kk][0] += r0; s1[kk][1] += r1; s1[kk][2] += r2; s1[kk][3] += r3;
-          s2[kk][0] += r0 * r0; s2[kk][1] += r1 * r1; s2[kk][2] += r2 * r2; s2[kk][3] += r3 * r3;
+          if (p_bnx) {
+            s2[kk][0] += r0 * bf16_lo(bx[k][0]); s2[kk][1] += r1 * bf16_hi(bx[k][0]);
+            s2[kk][2] += r2 * bf16_lo(bx[k][1]); s2[kk][3] += r3 * bf16_hi(bx[k][1]);
+          } else {
+            s2[kk][0] += r0 * r0; s2[kk][1] += r1 * r1; s2[kk][2] += r2 * r2; s2[kk][3] += r3 * r3;
+          }
         }
       }
     }

@@ -156,6 +156,7 @@ hipError_t launch_conv_gather(const GatherConvArgs& a, hipStream_t s) {
   if (a.Ci % 8 != 0 || a.Co % 4 != 0 || a.ntaps < 0 || a.ntaps > 9 || a.N * a.OH * a.OW <= 0 || a.Kw % 8 != 0)
     return hipErrorInvalidValue;
   if (conv_gather_wide_applies(a)) return launch_conv_gather_wide(a, s);
+  if (a.gate || a.bnx) return hipErrorInvalidValue;   // only the output stage of the wide kernels has them
   if (a.Co <= 16) return run_gather<256, 16, 4, 1>(a, s);
   if (a.Co <= 32) return run_gather<256, 32, 4, 1>(a, s);
   if (a.Co <= 64) return run_gather<128, 64, 2, 2>(a, s);
@@ -372,10 +373,34 @@ hipError_t conv_forward(const ConvShape& c, const bf16_t* x, const bf16_t* w, co
   return launch_conv_gather(a, s);
 }
 
+static hipError_t conv_dgrad_impl(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
+                                  const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, float* gsums, float* out_f32,
+                                  bf16_t* out_b16, hipStream_t s);
+
 hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                       const bf16_t* addmask, float* out_f32, bf16_t* out_b16, hipStream_t s) {
+  return conv_dgrad_impl(c, dy, wt, addend, addmask, nullptr, nullptr, nullptr, out_f32, out_b16, s);
+}
+
+// The gate and the sums live in the output stage of the wide kernels; every launch of this data gradient must be one.
+bool conv_dgrad_gates(const ConvShape& c) {
+  GatherConvArgs a{};
+  a.Hi = c.Ho(); a.Wi = c.Wo(); a.Ci = c.Co; a.Co = c.Cip; a.Kw = c.T * c.Co; a.ntaps = 1;
+  return conv_gather_wide_applies(a) && (c.stride == 1 || (c.Hi >= 2 && c.Wi >= 2));
+}
+
+hipError_t conv_dgrad_gated(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend, const bf16_t* gate,
+                            const bf16_t* bnx, float* gsums, float* out_f32, bf16_t* out_b16, hipStream_t s) {
+  if (!gate || !bnx || !gsums || !conv_dgrad_gates(c)) return hipErrorInvalidValue;
+  return conv_dgrad_impl(c, dy, wt, addend, nullptr, gate, bnx, gsums, out_f32, out_b16, s);
+}
+
+static hipError_t conv_dgrad_impl(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
+                                  const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, float* gsums, float* out_f32,
+                                  bf16_t* out_b16, hipStream_t s) {
   GatherConvArgs a{};
   a.in = dy; a.w = wt; a.addend = addend; a.addmask = addmask; a.out_f32 = out_f32; a.out_b16 = out_b16;
+  a.gate = gate; a.bnx = bnx; a.stats = gsums;
   a.N = c.N; a.Hi = c.Ho(); a.Wi = c.Wo(); a.Ci = c.Co;
   a.in_stride = 1;
   a.OHf = c.Hi; a.OWf = c.Wi;

@@ -26,6 +26,10 @@ struct GatherConvArgs {
   float* out_f32;        // optional fp32 output
   bf16_t* out_b16;       // optional bf16 output
   float* stats;          // optional [2*Co]: += per-channel sum and sum of squares of the bf16-rounded output
+  // Data gradient that ends in the ReLU and batch norm it back-propagates into next (wide kernels only):
+  const bf16_t* gate;    // optional (output indexing): the output is kept where gate > 0 and is zero elsewhere
+  const bf16_t* bnx;     // optional (output indexing), with stats: stats[Co + c] += sum of output * bnx instead of
+                         // the squares -- with stats[c] the two sums the batch-norm backward needs
   int N, Hi, Wi, Ci;
   int OH, OW, in_stride;
   int OHf, OWf, out_stride, ooh, oow;
@@ -76,6 +80,12 @@ hipError_t conv_forward(const ConvShape& c, const bf16_t* x, const bf16_t* w, co
 // dx[N,Hi,Wi,Cip] = conv^T(dy[N,Ho,Wo,Co], wt[Cip][T][Co]) (+ addend, optionally only where addmask > 0)
 hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                       const bf16_t* addmask, float* out_f32, bf16_t* out_b16, hipStream_t s);
+// The same, ending in the gate of the ReLU below and the two sums of the batch norm below it:
+//   dx = gate > 0 ? dgrad + addend : 0;  gsums[c] += sum bf16(dx[.., c]);  gsums[Cip + c] += sum bf16(dx[.., c]) * bnx[.., c].
+// Only where conv_dgrad_gates(c) (the wide kernels); hipErrorInvalidValue otherwise.
+bool conv_dgrad_gates(const ConvShape& c);
+hipError_t conv_dgrad_gated(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend, const bf16_t* gate,
+                            const bf16_t* bnx, float* gsums, float* out_f32, bf16_t* out_b16, hipStream_t s);
 // dw[Co][T][Ci] (+)= sum over pixels of dy * x.  overwrite = false: accumulated into dw (fp32 atomics where the
 // pixel dimension is split), dw zeroed by the caller;  overwrite = true: dw is written, whatever it held.
 // scratch (optional): device memory for the partial sums of the pixel splits; without it they are added
@@ -126,6 +136,8 @@ struct BnBwdArgs {
   float* dbeta;          // [C]
   int M, C;
   float eps;
+  int dy_gated;          // apply only: dy is already zero where the gate is closed (mask is not read)
+  int raw_sums;          // apply only: bsums holds sum g and sum g*x (not g*xhat), as a gated data gradient leaves them
 };
 hipError_t launch_bn_bwd_reduce(const BnBwdArgs& a, hipStream_t s);
 hipError_t launch_bn_bwd_apply(const BnBwdArgs& a, hipStream_t s);

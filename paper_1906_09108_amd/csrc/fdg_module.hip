@@ -4,6 +4,7 @@
 // by the kernels in conv_kernels.hip and stream_kernels.hip.
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 #include <new>
 #include <vector>
 
@@ -448,6 +449,46 @@ hipError_t bn_backward(const fdg_module* m, const SlotView& v, const BnInfo& b, 
   return launch_bn_bwd_apply(a, s);
 }
 
+// The same when dy came out of a gated data gradient (conv_dgrad_gated): it is already zero where the ReLU
+// was closed and the two sums are in the module's bsums, so only the apply pass runs.
+hipError_t bn_backward_after_gated_dgrad(const fdg_module* m, const SlotView& v, const BnInfo& b, const bf16_t* g,
+                                         const bf16_t* x, const float* addend, float* out_f32, bf16_t* out_b16,
+                                         hipStream_t s) {
+  BnBwdArgs a{};
+  a.dy = g; a.dy_is_f32 = 0; a.mask = nullptr; a.x = x; a.sums = v.sums(b);
+  a.gamma = v.snap(b.gamma_off);
+  a.bsums = m->bsums() + b.stat_off;
+  a.addend = addend; a.out_f32 = out_f32; a.out_b16 = out_b16;
+  a.dgamma = m->grads() + b.gamma_off; a.dbeta = m->grads() + b.beta_off;
+  a.M = b.M; a.C = b.C; a.eps = m->p.d.bn_eps;
+  a.dy_gated = 1; a.raw_sums = 1;
+  ProfScope ps(m, PC_BN_BWD, 0, (double)b.M * b.C * ((out_f32 || out_b16 ? 4 : 0) + (addend ? 4 : 0) + (out_f32 ? 4 : 0) +
+                                                     (out_b16 ? 2 : 0)), s);
+  return launch_bn_bwd_apply(a, s);
+}
+
+// Data gradient of convolution c into g (bf16), then the backward of the ReLU (gate = its output) and of the batch
+// norm b (input x) that precede the convolution.  Where the wide kernels run, the gate and the two sums of the
+// batch-norm backward are taken in the data gradient's output stage and one pass over g is saved.
+hipError_t dgrad_relu_bn_backward(const fdg_module* m, const SlotView& v, const ConvInfo& c, const bf16_t* dy, const bf16_t* wt,
+                                  const float* dgrad_addend, const BnInfo& b, const bf16_t* gate, const bf16_t* x, bf16_t* g,
+                                  const float* bn_addend, float* out_f32, bf16_t* out_b16, hipStream_t s) {
+  static const bool unfused = getenv("FDG_NO_GATED_DGRAD") != nullptr;   // A/B switch for measurements
+  if (!unfused && conv_dgrad_gates(c.sh) && b.C == c.sh.Cip) {
+    {
+      const double bytes = 2 * conv_out_elems(c.sh) + 2 * conv_w_elems(c.sh) + conv_in_elems(c.sh) * ((dgrad_addend ? 4 : 0) + 2 + 2 + 2);
+      ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c.sh), bytes, s);
+      const hipError_t e = conv_dgrad_gated(c.sh, dy, wt, dgrad_addend, gate, x, m->bsums() + b.stat_off, nullptr, g, s);
+      ps.label(c.sh);
+      if (e != hipSuccess) return e;
+    }
+    return bn_backward_after_gated_dgrad(m, v, b, g, x, bn_addend, out_f32, out_b16, s);
+  }
+  hipError_t e = mconv_dgrad(m, c, dy, wt, dgrad_addend, nullptr, nullptr, g, s);
+  if (e != hipSuccess) return e;
+  return bn_backward(m, v, b, g, false, gate, x, bn_addend, out_f32, out_b16, s);
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------------------------------------
@@ -648,8 +689,7 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
       // final ReLU mask (y > 0) then BN2
       FDG_TRY(bn_backward(m, v, b2, m->G(cur), true, t_y, t_c2, nullptr, nullptr, m->T(0), s));
       FDG_TRY(mconv_wgrad(m, c2, t_a1, m->T(0), s));
-      FDG_TRY(mconv_dgrad(m, c2, m->T(0), v.Wt(c2), nullptr, nullptr, nullptr, m->T(1), s));
-      FDG_TRY(bn_backward(m, v, b1, m->T(1), false, t_a1, t_c1, nullptr, nullptr, m->T(0), s));
+      FDG_TRY(dgrad_relu_bn_backward(m, v, c2, m->T(0), v.Wt(c2), nullptr, b1, t_a1, t_c1, m->T(1), nullptr, nullptr, m->T(0), s));
       FDG_TRY(mconv_wgrad(m, c1, in_b, m->T(0), s));
       if (L.projects) {
         const ConvInfo& cp = p.convs[L.conv[2]];
@@ -669,20 +709,17 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
       const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]];
       const bf16_t *t_o1 = v.act(L.act[0]), *t_c1 = v.act(L.act[1]), *t_o2 = v.act(L.act[2]);
       FDG_TRY(mconv_wgrad(m, c2, t_o2, m->GB(cur), s));
-      FDG_TRY(mconv_dgrad(m, c2, m->GB(cur), v.Wt(c2), nullptr, nullptr, nullptr, m->T(0), s));
-      FDG_TRY(bn_backward(m, v, b2, m->T(0), false, t_o2, t_c1, nullptr, nullptr, m->T(1), s));
+      FDG_TRY(dgrad_relu_bn_backward(m, v, c2, m->GB(cur), v.Wt(c2), nullptr, b2, t_o2, t_c1, m->T(0), nullptr, nullptr, m->T(1), s));
       FDG_TRY(mconv_wgrad(m, c1, t_o1, m->T(1), s));
       if (L.projects) {
         const ConvInfo& cp = p.convs[L.conv[2]];
         FDG_TRY(mconv_wgrad(m, cp, t_o1, m->GB(cur), s));
         FDG_TRY(mconv_dgrad(m, cp, m->GB(cur), v.Wt(cp), nullptr, nullptr, m->TP(), nullptr, s));
-        FDG_TRY(mconv_dgrad(m, c1, m->T(1), v.Wt(c1), m->TP(), nullptr, nullptr, m->T(0), s));
-        FDG_TRY(bn_backward(m, v, b1, m->T(0), false, t_o1, in_b, nullptr, need_dx ? m->G(nxt) : nullptr,
-                            need_dx ? m->GB(nxt) : nullptr, s));
+        FDG_TRY(dgrad_relu_bn_backward(m, v, c1, m->T(1), v.Wt(c1), m->TP(), b1, t_o1, in_b, m->T(0), nullptr,
+                                       need_dx ? m->G(nxt) : nullptr, need_dx ? m->GB(nxt) : nullptr, s));
       } else {
-        FDG_TRY(mconv_dgrad(m, c1, m->T(1), v.Wt(c1), nullptr, nullptr, nullptr, m->T(0), s));
-        FDG_TRY(bn_backward(m, v, b1, m->T(0), false, t_o1, in_b, m->G(cur), need_dx ? m->G(nxt) : nullptr,
-                            need_dx ? m->GB(nxt) : nullptr, s));
+        FDG_TRY(dgrad_relu_bn_backward(m, v, c1, m->T(1), v.Wt(c1), nullptr, b1, t_o1, in_b, m->T(0), m->G(cur),
+                                       need_dx ? m->G(nxt) : nullptr, need_dx ? m->GB(nxt) : nullptr, s));
       }
     }
     cur = nxt;

@@ -34,6 +34,23 @@ int fdgk_conv_dgrad(const void* dy_b16, const void* wt_b16, const float* addend_
                          static_cast<const bf16_t*>(addmask_b16), dx_f32, static_cast<bf16_t*>(dx_b16), st(hip_stream));
 }
 
+int fdgk_conv_dgrad_gated(const void* dy_b16, const void* wt_b16, const float* addend_f32, const void* gate_b16,
+                          const void* bnx_b16, float* gsums_f32, float* dx_f32, void* dx_b16, int n, int h, int w, int ci,
+                          int co, int ksize, int stride, void* hip_stream) {
+  ConvShape c;
+  if (!dy_b16 || !wt_b16 || !gate_b16 || !bnx_b16 || !gsums_f32 || (!dx_f32 && !dx_b16) ||
+      !conv_shape(c, n, h, w, ci, co, ksize, stride))
+    return (int)hipErrorInvalidValue;
+  return (int)conv_dgrad_gated(c, static_cast<const bf16_t*>(dy_b16), static_cast<const bf16_t*>(wt_b16), addend_f32,
+                               static_cast<const bf16_t*>(gate_b16), static_cast<const bf16_t*>(bnx_b16), gsums_f32, dx_f32,
+                               static_cast<bf16_t*>(dx_b16), st(hip_stream));
+}
+
+int fdgk_conv_dgrad_gates(int n, int h, int w, int ci, int co, int ksize, int stride) {
+  ConvShape c;
+  return conv_shape(c, n, h, w, ci, co, ksize, stride) && conv_dgrad_gates(c) ? 1 : 0;
+}
+
 size_t fdgk_conv_wgrad_scratch_bytes(int n, int h, int w, int ci, int co, int ksize, int stride) {
   ConvShape c;
   if (!conv_shape(c, n, h, w, ci, co, ksize, stride)) return 0;
@@ -76,6 +93,19 @@ int fdgk_bn_bwd(const void* dy, int dy_is_f32, const void* mask_b16, const void*
   a.dgamma = dgamma; a.dbeta = dbeta; a.M = m; a.C = c; a.eps = eps;
   hipError_t e = launch_bn_bwd_reduce(a, st(hip_stream));
   if (e != hipSuccess) return (int)e;
+  return (int)launch_bn_bwd_apply(a, st(hip_stream));
+}
+
+int fdgk_bn_bwd_gated(const void* g_b16, const void* x_b16, const float* sums_f32, const float* gamma,
+                      const float* gsums_f32, const float* addend_f32, float* dx_f32, void* dx_b16, float* dgamma,
+                      float* dbeta, int m, int c, float eps, void* hip_stream) {
+  if (!g_b16 || !x_b16 || !sums_f32 || !gamma || !gsums_f32 || !dgamma || !dbeta) return (int)hipErrorInvalidValue;
+  BnBwdArgs a{};
+  a.dy = g_b16; a.dy_is_f32 = 0; a.mask = nullptr; a.x = static_cast<const bf16_t*>(x_b16); a.sums = sums_f32;
+  a.gamma = gamma; a.bsums = const_cast<float*>(gsums_f32);
+  a.addend = addend_f32; a.out_f32 = dx_f32; a.out_b16 = static_cast<bf16_t*>(dx_b16);
+  a.dgamma = dgamma; a.dbeta = dbeta; a.M = m; a.C = c; a.eps = eps;
+  a.dy_gated = 1; a.raw_sums = 1;
   return (int)launch_bn_bwd_apply(a, st(hip_stream));
 }
 

@@ -241,6 +241,7 @@ __device__ __forceinline__ void load_masked_dy(const void* dy, const bf16_t* mas
     load8_f32(reinterpret_cast<const float*>(dy) + o, g);
   else
     unpack8(*reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(dy) + o), g);
+  if (!mask) return;   // dy was gated where it was produced
   float mk[8];
   unpack8(*reinterpret_cast<const uint4*>(mask + o), mk);
 #pragma unroll
@@ -317,19 +318,20 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(BnBwdArgs a, int
     load8_f32(a.gamma + c0, gm);
     load8_f32(a.bsums + c0, b1);
     load8_f32(a.bsums + C + c0, b2);
-    if (blockIdx.y == 0 && rl == 0) {
-      store8_f32(a.dbeta + c0, b1);
-      store8_f32(a.dgamma + c0, b2);
-    }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const float mean = s1[i] * invM;
       const float var = fmaxf(s2[i] * invM - mean * mean, 0.f);
       const float is = rsqrtf(var + a.eps);
+      if (a.raw_sums) b2[i] = is * (b2[i] - mean * b1[i]);   // sum g*xhat from sum g*x and sum g
       gi[i] = gm[i] * is;
       const float k1 = b1[i] * invM, k2 = b2[i] * invM;
       pa[i] = -gi[i] * k2 * is;
       pb[i] = -gi[i] * k1 + gi[i] * k2 * is * mean;
+    }
+    if (blockIdx.y == 0 && rl == 0) {
+      store8_f32(a.dbeta + c0, b1);
+      store8_f32(a.dgamma + c0, b2);
     }
   }
   if (!a.out_f32 && !a.out_b16) return;
@@ -353,8 +355,10 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(BnBwdArgs a, int
   }
 }
 
-hipError_t launch_bn_bwd_apply(const BnBwdArgs& a, hipStream_t s) {
-  if (a.C % 8 != 0 || a.C > 2048 || a.M <= 0 || !a.mask) return hipErrorInvalidValue;
+hipError_t launch_bn_bwd_apply(const BnBwdArgs& a_in, hipStream_t s) {
+  BnBwdArgs a = a_in;
+  if (a.dy_gated) a.mask = nullptr;
+  if (a.C % 8 != 0 || a.C > 2048 || a.M <= 0 || (!a.mask && !a.dy_gated)) return hipErrorInvalidValue;
   const auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
   if (!al16(a.sums) || !al16(a.gamma) || !al16(a.bsums) || !al16(a.dgamma) || !al16(a.dbeta)) return hipErrorInvalidValue;
   ApplyShape r = apply_shape(a.M, a.C);

@@ -6,7 +6,7 @@ import ctypes
 
 from .binding import _ptr, _stream_handle, load
 
-KERNEL_EXPORTS = ["fdgk_conv_fwd", "fdgk_conv_dgrad", "fdgk_conv_wgrad", "fdgk_conv_wgrad_scratch_bytes", "fdgk_bn_stats", "fdgk_bn_apply",
+KERNEL_EXPORTS = ["fdgk_conv_fwd", "fdgk_conv_dgrad", "fdgk_conv_dgrad_gated", "fdgk_conv_dgrad_gates", "fdgk_bn_bwd_gated", "fdgk_conv_wgrad", "fdgk_conv_wgrad_scratch_bytes", "fdgk_bn_stats", "fdgk_bn_apply",
                   "fdgk_bn_bwd", "fdgk_sgd"]
 _ready = False
 
@@ -18,6 +18,9 @@ def _lib():
         vp, i, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
         lib.fdgk_conv_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
         lib.fdgk_conv_dgrad.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
+        lib.fdgk_conv_dgrad_gated.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
+        lib.fdgk_conv_dgrad_gates.argtypes = [i, i, i, i, i, i, i]
+        lib.fdgk_bn_bwd_gated.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, f, vp]
         lib.fdgk_conv_wgrad.argtypes = [vp, vp, vp, vp, sz, i, i, i, i, i, i, i, i, vp]
         lib.fdgk_conv_wgrad_scratch_bytes.argtypes = [i, i, i, i, i, i, i]
         lib.fdgk_bn_stats.argtypes = [vp, vp, i, i, vp]
@@ -44,6 +47,24 @@ def fdgk_conv_fwd(x_b16, w_b16, addend_f32, y_f32, y_b16, stats_f32, n, h, w, ci
 def fdgk_conv_dgrad(dy_b16, wt_b16, addend_f32, addmask_b16, dx_f32, dx_b16, n, h, w, ci, co, ksize, stride, stream=None):
     _ok(_lib().fdgk_conv_dgrad(_ptr(dy_b16), _ptr(wt_b16), _ptr(addend_f32), _ptr(addmask_b16), _ptr(dx_f32),
                                _ptr(dx_b16), n, h, w, ci, co, ksize, stride, _stream_handle(stream)), "fdgk_conv_dgrad")
+
+
+def fdgk_conv_dgrad_gates(n, h, w, ci, co, ksize, stride) -> bool:
+    return bool(_lib().fdgk_conv_dgrad_gates(n, h, w, ci, co, ksize, stride))
+
+
+def fdgk_conv_dgrad_gated(dy_b16, wt_b16, addend_f32, gate_b16, bnx_b16, gsums_f32, dx_f32, dx_b16, n, h, w, ci, co, ksize,
+                          stride, stream=None):
+    _ok(_lib().fdgk_conv_dgrad_gated(_ptr(dy_b16), _ptr(wt_b16), _ptr(addend_f32), _ptr(gate_b16), _ptr(bnx_b16),
+                                     _ptr(gsums_f32), _ptr(dx_f32), _ptr(dx_b16), n, h, w, ci, co, ksize, stride,
+                                     _stream_handle(stream)), "fdgk_conv_dgrad_gated")
+
+
+def fdgk_bn_bwd_gated(g_b16, x_b16, sums_f32, gamma, gsums_f32, addend_f32, dx_f32, dx_b16, dgamma, dbeta, m, c, eps,
+                      stream=None):
+    _ok(_lib().fdgk_bn_bwd_gated(_ptr(g_b16), _ptr(x_b16), _ptr(sums_f32), _ptr(gamma), _ptr(gsums_f32), _ptr(addend_f32),
+                                 _ptr(dx_f32), _ptr(dx_b16), _ptr(dgamma), _ptr(dbeta), m, c, eps, _stream_handle(stream)),
+        "fdgk_bn_bwd_gated")
 
 
 def fdgk_conv_wgrad_scratch_bytes(n, h, w, ci, co, ksize, stride) -> int:

@@ -146,6 +146,85 @@ def test_conv_dgrad(case):
     assert rel(nhwc_to_nchw(dx32), full + add * (mask > 0)) <= F32_TOL
 
 
+GATED_CASES = [  # data gradients the wide kernels run: output (= layer input) channels >= 128, co % 64 == 0
+    (2, 8, 8, 128, 64, 3, 1),
+    (3, 7, 5, 160, 128, 3, 1),      # ragged pixel tile, 160-wide tile
+    (16, 8, 8, 640, 640, 3, 1),     # patch form
+    (3, 9, 7, 192, 320, 3, 2),      # four parity classes, odd sizes
+    (2, 8, 8, 320, 640, 1, 2),      # three of the four classes have no tap: zeros (plus addend) gated
+    (5, 4, 4, 128, 192, 1, 1),
+]
+
+
+@pytest.mark.parametrize("case", GATED_CASES)
+def test_gated_data_gradient_feeds_the_batch_norm_backward(case):
+    """conv_dgrad_gated leaves g = gate > 0 ? dgrad + addend : 0 and the sums [sum g, sum g*x] of its bf16 values;
+    bn_bwd_gated turns them into dgamma, dbeta and dx.  Reference: the oracle's data gradient, the gate and the
+    rounding applied in numpy, then the oracle's batch-norm backward on that rounded g."""
+    from paper_1906_09108_amd import kernels as K
+    t = _torch()
+    n, h, w, ci, co, k, s = case
+    print("gated dgrad", case, flush=True)
+    assert K.fdgk_conv_dgrad_gates(n, h, w, ci, co, k, s)
+    x_unused, wt, dy, ho, wo = _conv_data(case, 11)
+    r = np.random.default_rng(12)
+    ref = K32.conv_bwd_data(dy, wt, x_unused.shape, s, 1 if k == 3 else 0).astype(np.float64)
+    add = r.standard_normal(ref.shape).astype(np.float32) * 0.5
+    gate = bf16_round(np.maximum(r.standard_normal(ref.shape), 0))            # a ReLU output: about half closed
+    bnx = bf16_round(r.standard_normal(ref.shape) * (0.5 + r.random((1, ci, 1, 1))) + r.standard_normal((1, ci, 1, 1)))
+    dyd = to_dev_nhwc_b16(dy)
+    wtd = t.from_numpy(wt.transpose(1, 2, 3, 0).copy()).to(t.bfloat16).contiguous().cuda()
+    gsums = t.zeros(2 * ci, dtype=t.float32, device="cuda")
+    g32 = t.full((n, h, w, ci), float("nan"), dtype=t.float32, device="cuda")
+    g16 = t.zeros((n, h, w, ci), dtype=t.bfloat16, device="cuda")
+    K.fdgk_conv_dgrad_gated(dyd, wtd, to_dev_nhwc_f32(add), to_dev_nhwc_b16(gate), to_dev_nhwc_b16(bnx), gsums, g32, g16,
+                            n, h, w, ci, co, k, s)
+    t.cuda.synchronize()
+    g_ref = (ref + add) * (gate > 0)
+    assert rel(nhwc_to_nchw(g32), g_ref) <= F32_TOL
+    assert rel(nhwc_to_nchw(g16), g_ref) <= B16_TOL
+    assert np.all(nhwc_to_nchw(g32)[gate <= 0] == 0)
+    # the sums are those of the bf16 values written (holds exactly up to summation order)
+    gb = g16.to(t.float64).reshape(-1, ci).cpu().numpy()
+    xb = to_dev_nhwc_b16(bnx).to(t.float64).reshape(-1, ci).cpu().numpy()
+    got = gsums.cpu().numpy().astype(np.float64)
+    assert rel(got[:ci], gb.sum(0)) <= 1e-5
+    assert rel(got[ci:], (gb * xb).sum(0)) <= 1e-5
+    # batch-norm backward from those sums against the oracle's on the same rounded g
+    m = n * h * w
+    eps = 1e-5
+    gamma = (1 + 0.2 * r.standard_normal(ci)).astype(np.float32)
+    x4 = xb.T.reshape(1, ci, m, 1).astype(np.float32)
+    _, mean, var, invstd = K32.bn_fwd(x4, gamma, np.zeros(ci, np.float32), eps)
+    dx_ref, dgamma_ref, dbeta_ref = K32.bn_bwd(x4, gb.T.reshape(1, ci, m, 1).astype(np.float32), gamma, mean, invstd)
+    xd = to_dev_nhwc_b16(bnx).reshape(m, ci)
+    sums = t.zeros(2 * ci, dtype=t.float32, device="cuda")
+    K.fdgk_bn_stats(xd, sums, m, ci)
+    res = r.standard_normal((m, ci)).astype(np.float32)
+    dx32 = t.empty((m, ci), dtype=t.float32, device="cuda")
+    dx16 = t.empty((m, ci), dtype=t.bfloat16, device="cuda")
+    dg, db = t.empty(ci, dtype=t.float32, device="cuda"), t.empty(ci, dtype=t.float32, device="cuda")
+    K.fdgk_bn_bwd_gated(g16.reshape(m, ci), xd, sums, t.from_numpy(gamma).cuda(), gsums, t.from_numpy(res).cuda(), dx32, dx16,
+                        dg, db, m, ci, eps)
+    t.cuda.synchronize()
+    assert rel(db.cpu().numpy(), dbeta_ref.astype(np.float64)) <= F32_TOL
+    assert rel(dg.cpu().numpy(), dgamma_ref.astype(np.float64)) <= F32_TOL
+    dref = dx_ref.reshape(ci, m).T.astype(np.float64) + res
+    assert rel(dx32.cpu().numpy(), dref) <= F32_TOL
+    assert rel(dx16.to(t.float32).cpu().numpy(), dref) <= B16_TOL
+
+
+def test_gated_data_gradient_refuses_narrow_layers():
+    from paper_1906_09108_amd import kernels as K
+    t = _torch()
+    assert not K.fdgk_conv_dgrad_gates(2, 8, 8, 16, 16, 3, 1)
+    z = t.zeros(2 * 8 * 8 * 16, dtype=t.bfloat16, device="cuda")
+    w = t.zeros(16 * 9 * 16, dtype=t.bfloat16, device="cuda")
+    st = t.zeros(32, dtype=t.float32, device="cuda")
+    with pytest.raises(RuntimeError):
+        K.fdgk_conv_dgrad_gated(z, w, None, z, z, st, None, z, 2, 8, 8, 16, 16, 3, 1)
+
+
 @pytest.mark.parametrize("case", CONV_CASES)
 def test_conv_wgrad(case):
     from paper_1906_09108_amd import kernels as K
