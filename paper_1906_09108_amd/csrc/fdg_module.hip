@@ -297,9 +297,33 @@ struct Profiler {
   ~Profiler() { for (hipEvent_t e : pool) (void)hipEventDestroy(e); }
 };
 
+// Weight gradients run on a second stream of the module.  A weight gradient depends only on tensors that exist
+// when it is launched and nothing but the update needs its result, so it may overlap the data-gradient / batch-norm
+// chain that follows it: while the workgroups of one kernel are in their HBM-bound output stage (or its grid
+// leaves compute units idle), workgroups of the other keep the matrix cores busy.  Two rules keep it correct:
+// the side stream waits for everything enqueued on the caller's stream before the launch, and a kernel on the
+// caller's stream that overwrites a buffer a pending weight gradient reads first waits for that weight gradient.
+struct SideStream {
+  hipStream_t stream = nullptr;
+  hipEvent_t ready = nullptr, joined = nullptr;
+  struct Reader { const void* buf = nullptr; hipEvent_t done = nullptr; bool active = false; };
+  Reader readers[4];
+  bool busy = false;
+  bool usable = false;
+  ~SideStream() {
+    if (stream) { (void)hipStreamSynchronize(stream); (void)hipStreamDestroy(stream); }
+    if (ready) (void)hipEventDestroy(ready);
+    if (joined) (void)hipEventDestroy(joined);
+    for (Reader& r : readers)
+      if (r.done) (void)hipEventDestroy(r.done);
+    (void)hipGetLastError();
+  }
+};
+
 struct fdg_module {
   Plan p;
   mutable Profiler prof;
+  mutable SideStream side;
   char* ws = nullptr;
   int64_t seq_fwd = 0, seq_bwd = 0;
   bool has_grad = false;
@@ -389,8 +413,42 @@ hipError_t mconv_forward(const fdg_module* m, const ConvInfo& c, const bf16_t* x
   ps.label(c.sh);
   return e;
 }
+// ---- the side stream of the weight gradients (see SideStream) ----
+bool side_create(SideStream& sd) {
+  static const bool off = getenv("FDG_NO_OVERLAP") != nullptr;   // A/B switch for measurements
+  if (off) return true;
+  bool ok = hipStreamCreateWithFlags(&sd.stream, hipStreamNonBlocking) == hipSuccess;
+  ok = ok && hipEventCreateWithFlags(&sd.ready, hipEventDisableTiming) == hipSuccess;
+  ok = ok && hipEventCreateWithFlags(&sd.joined, hipEventDisableTiming) == hipSuccess;
+  for (SideStream::Reader& r : sd.readers) ok = ok && hipEventCreateWithFlags(&r.done, hipEventDisableTiming) == hipSuccess;
+  sd.usable = ok;
+  if (!ok) (void)hipGetLastError();
+  return ok;
+}
+// `s` waits for the pending weight gradient that reads `buf`, if there is one: call before overwriting buf.
+hipError_t side_wait_readers(const fdg_module* m, const void* buf, hipStream_t s) {
+  if (!buf) return hipSuccess;
+  for (SideStream::Reader& r : m->side.readers)
+    if (r.active && r.buf == buf) {
+      r.active = false;
+      return hipStreamWaitEvent(s, r.done, 0);
+    }
+  return hipSuccess;
+}
+// `s` waits for everything on the side stream (end of a backward; start of any other call after a failed one).
+hipError_t side_join(const fdg_module* m, hipStream_t s) {
+  SideStream& sd = m->side;
+  if (!sd.busy) return hipSuccess;
+  hipError_t e = hipEventRecord(sd.joined, sd.stream);
+  if (e == hipSuccess) e = hipStreamWaitEvent(s, sd.joined, 0);
+  for (SideStream::Reader& r : sd.readers) r.active = false;
+  sd.busy = false;
+  return e;
+}
+
 hipError_t mconv_dgrad(const fdg_module* m, const ConvInfo& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                        const bf16_t* addmask, float* out_f32, bf16_t* out_b16, hipStream_t s) {
+  if (hipError_t e = side_wait_readers(m, out_b16, s); e != hipSuccess) return e;
   const double bytes = 2 * conv_out_elems(c.sh) + 2 * conv_w_elems(c.sh) +
                        conv_in_elems(c.sh) * ((addend ? 4 : 0) + (addmask ? 2 : 0) + (out_f32 ? 4 : 0) + (out_b16 ? 2 : 0));
   ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c.sh), bytes, s);
@@ -400,6 +458,28 @@ hipError_t mconv_dgrad(const fdg_module* m, const ConvInfo& c, const bf16_t* dy,
 }
 hipError_t mconv_wgrad(const fdg_module* m, const ConvInfo& c, const bf16_t* x, const bf16_t* dy, hipStream_t s) {
   const double bytes = 2 * conv_in_elems(c.sh) + 2 * conv_out_elems(c.sh) + 4.0 * c.sh.Co * c.sh.T * c.sh.Ci;
+  SideStream& sd = m->side;
+  if (sd.usable && !m->prof.on) {   // while timing kernels everything stays on one stream: a kernel's time is its own
+    hipError_t e = hipEventRecord(sd.ready, s);
+    if (e == hipSuccess) e = hipStreamWaitEvent(sd.stream, sd.ready, 0);
+    if (e != hipSuccess) return e;
+    sd.busy = true;
+    e = conv_wgrad(c.sh, x, dy, m->grads() + c.p_off, reinterpret_cast<float*>(m->ws + m->p.o_wscratch), m->p.wscratch_bytes,
+                   /*overwrite=*/true, sd.stream);
+    if (e != hipSuccess) return e;
+    // remember who reads dy: the entry of the same buffer (its earlier reader ran before this one on the side
+    // stream), else a free one, else the whole side stream is waited for at the next overwrite of anything
+    SideStream::Reader* slot = nullptr;
+    for (SideStream::Reader& r : sd.readers)
+      if (r.active && r.buf == dy) slot = &r;
+    if (!slot)
+      for (SideStream::Reader& r : sd.readers)
+        if (!r.active) { slot = &r; break; }
+    if (!slot) return side_join(m, s);
+    slot->buf = dy;
+    slot->active = true;
+    return hipEventRecord(slot->done, sd.stream);
+  }
   ProfScope ps(m, PC_CONV_WGRAD, conv_flops(c.sh), bytes, s);
   const hipError_t e = conv_wgrad(c.sh, x, dy, m->grads() + c.p_off, reinterpret_cast<float*>(m->ws + m->p.o_wscratch),
                                   m->p.wscratch_bytes, /*overwrite=*/true, s);
@@ -440,6 +520,7 @@ hipError_t bn_backward(const fdg_module* m, const SlotView& v, const BnInfo& b, 
   a.addend = addend; a.out_f32 = out_f32; a.out_b16 = out_b16;
   a.dgamma = m->grads() + b.gamma_off; a.dbeta = m->grads() + b.beta_off;
   a.M = b.M; a.C = b.C; a.eps = m->p.d.bn_eps;
+  if (hipError_t e = side_wait_readers(m, out_b16, s); e != hipSuccess) return e;
   // the reduce pass reads dy, gate and x; the apply pass reads them again and writes dx
   const double rd = (dy_f32 ? 4 : 2) + 2 + 2;
   ProfScope ps(m, PC_BN_BWD, 0, (double)b.M * b.C * (rd + ((out_f32 || out_b16) ? rd : 0) + (addend ? 4 : 0) +
@@ -462,6 +543,7 @@ hipError_t bn_backward_after_gated_dgrad(const fdg_module* m, const SlotView& v,
   a.dgamma = m->grads() + b.gamma_off; a.dbeta = m->grads() + b.beta_off;
   a.M = b.M; a.C = b.C; a.eps = m->p.d.bn_eps;
   a.dy_gated = 1; a.raw_sums = 1;
+  if (hipError_t e = side_wait_readers(m, out_b16, s); e != hipSuccess) return e;
   ProfScope ps(m, PC_BN_BWD, 0, (double)b.M * b.C * ((out_f32 || out_b16 ? 4 : 0) + (addend ? 4 : 0) + (out_f32 ? 4 : 0) +
                                                      (out_b16 ? 2 : 0)), s);
   return launch_bn_bwd_apply(a, s);
@@ -475,6 +557,7 @@ hipError_t dgrad_relu_bn_backward(const fdg_module* m, const SlotView& v, const 
                                   const float* bn_addend, float* out_f32, bf16_t* out_b16, hipStream_t s) {
   static const bool unfused = getenv("FDG_NO_GATED_DGRAD") != nullptr;   // A/B switch for measurements
   if (!unfused && conv_dgrad_gates(c.sh) && b.C == c.sh.Cip) {
+    if (hipError_t e = side_wait_readers(m, g, s); e != hipSuccess) return e;
     {
       const double bytes = 2 * conv_out_elems(c.sh) + 2 * conv_w_elems(c.sh) + conv_in_elems(c.sh) * ((dgrad_addend ? 4 : 0) + 2 + 2 + 2);
       ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c.sh), bytes, s);
@@ -521,6 +604,7 @@ fdg_status fdg_module_create(const fdg_module_desc* desc, void* dev_workspace, s
   m->ws = static_cast<char*>(dev_workspace);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   m->last_stream = s;
+  (void)side_create(m->side);   // without it the weight gradients simply stay on the caller's stream
   const Plan& p = m->p;
   // parameters, momentum, gradients, backward sums, running statistics (mean 0, var 1), emit table
   hipError_t e = launch_fill_zero(m->ws, p.o_running, s);
@@ -558,6 +642,7 @@ fdg_status fdg_forward(fdg_module* m, const float* x_dev, const int32_t* labels_
   if (m->seq_fwd - m->seq_bwd >= p.d.delay + 1) return FDG_ERR_QUEUE_FULL;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   m->last_stream = s;
+  FDG_TRY(side_join(m, s));
   SlotView v{m, m->slot(m->seq_fwd)};
   const int N = p.d.n;
   // snapshot of the weights this forward uses (Eq. 10 evaluates the backward at these)
@@ -655,6 +740,7 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
   const int N = p.d.n;
   // the backward sums of batch norm accumulate with atomics and start at zero; every gradient is written
   // (not accumulated) by the kernel that produces it
+  FDG_TRY(side_join(m, s));
   FDG_TRY(launch_fill_zero(m->ws + p.o_bsums, p.o_running - p.o_bsums, s));
   int cur = 0;
   if (!p.is_top)  // gradient shrinking of Eq. 15: multiply by beta before anything else
@@ -674,6 +760,7 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
         FDG_TRY(launch_pool_bwd(dp, m->TP(), nullptr, N, p.head_HW, p.head_C, s));
         FDG_TRY(bn_backward(m, v, b0, m->TP(), true, v.act(L.act[0]), in_b, nullptr, m->G(nxt), m->GB(nxt), s));
       } else {
+        FDG_TRY(side_wait_readers(m, m->GB(nxt), s));
         FDG_TRY(launch_pool_bwd(dp, m->G(nxt), m->GB(nxt), N, p.head_HW, p.head_C, s));
       }
     } else if (L.kind == FDG_STEM_CONV_BN_RELU) {
@@ -726,6 +813,7 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
   }
   if (grad_in_dev && !p.d.is_bottom)
     FDG_TRY(launch_nhwc_to_nchw(m->G(cur), grad_in_dev, N, p.d.c_in, p.d.h_in * p.d.w_in, p.Cp_in, s));
+  FDG_TRY(side_join(m, s));   // the gradient is complete when the call's stream gets here
   ++m->seq_bwd;
   m->has_grad = true;
   return FDG_OK;
@@ -736,6 +824,7 @@ fdg_status fdg_update(fdg_module* m, float lr, void* hip_stream) {
   if (!m->has_grad) return FDG_ERR_NO_GRAD;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   m->last_stream = s;
+  FDG_TRY(side_join(m, s));
   {
     ProfScope ps(m, PC_SGD, 0, 20.0 * m->p.P, s);   // read theta, v, g; write theta, v
     FDG_TRY(launch_sgd(m->params(), m->mom(), m->grads(), m->p.P, lr, m->p.d.momentum, m->p.d.weight_decay, s));

@@ -10,7 +10,7 @@ Three runs advance in lock step, as in tests/gpu_harness.py: the HIP chain, the 
     relL2(gpu, same) <= 2e-2 + 2 relL2(same, plain), since after the first update the two bf16 evaluations
     round their weights independently;
   * Eq. 16 / Eq. 17 on the device: with frozen weights the gradient of module k under beta is beta^(K-k) times
-    the gradient under beta = 1;
+    the gradient under beta = 1 (up to one bf16 rounding: the order of atomic sums is not fixed);
   * the loss goes down on separable data.
 """
 import numpy as np
@@ -94,8 +94,10 @@ def test_chain_against_the_oracle(K):
 
 def test_chain_compounds_the_shrinking_factor():
     """Eq. 16 / Eq. 17 on the device, weights frozen (lr = 0): g_hat(module k; beta) = beta^(K-1-k) g_hat(module k; 1),
-    k counted from 0.  beta = 0.5 scales every intermediate by a power of two, so only the order of the
-    atomic sums of the weight gradient differs between the two runs."""
+    k counted from 0.  beta = 0.5 scales every intermediate by a power of two, so the two runs differ only through
+    the order of fp32 atomic sums (batch-norm reductions, weight gradients).  A last-bit difference in such a sum
+    can move one bf16 rounding of an intermediate gradient (2^-9 of that element), which is what the bound allows;
+    two runs with the SAME beta differ by as much (measured: up to 3e-4)."""
     t = _torch()
     from paper_1906_09108_amd import FdgChain
     K = 3
@@ -119,7 +121,7 @@ def test_chain_compounds_the_shrinking_factor():
     for k in range(K):
         ref = runs[1.0][k] * 0.5 ** (K - 1 - k)
         assert np.abs(ref).max() > 0
-        assert rel_err(runs[0.5][k], ref) <= 1e-5, (k, rel_err(runs[0.5][k], ref))
+        assert rel_err(runs[0.5][k], ref) <= 2.0 ** -9, (k, rel_err(runs[0.5][k], ref))
 
 
 def test_chain_learns_separable_data():
