@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 # from the committed summaries under profiles/ (None where not measured)
 TRAFFIC_BYTES = {
     # profiles/hbm_traffic_conv_kernels_cfg4.md: FETCH_SIZE + WRITE_SIZE, scaled by the 1 GiB copy calibration
-    (4, "conv_patch_kernel<160, 160, 5> 640>640 k3 s1 @8x8"): 93.0e6,
+    (4, "conv_patch_kernel<160, 160, 5> 640>640 k3 s1 @8x8"): 103.6e6,
 }
 
 
