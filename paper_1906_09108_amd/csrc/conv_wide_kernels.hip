@@ -45,7 +45,9 @@ __device__ __forceinline__ void wait_vmcnt() {
 // accumulator blocks of 32x32; wk = wave >> 1 takes one 32-channel half of every 64-channel k-chunk.  So a
 // wave reads 2 + BN/32 operand fragments for every 2 * BN/32 MFMAs (the best ratio four waves can get on a
 // 128 x 160 tile) and the two k-halves are added once, through LDS, after the main loop.
-template <int BN, int STAGES>
+// KTAIL: the input channels are not a multiple of 64 (WRN's 160): the last 64-channel chunk of every tap is
+// partly beyond the tensor, and those 16-byte units are loaded from the zero word, for pixels and weights alike.
+template <int BN, int STAGES, bool KTAIL>
 __global__ __launch_bounds__(256) void conv_gather_dma_kernel(GatherConvArgs a, int m_tiles, int n_tiles) {
   constexpr int BM = 128;
   static_assert(BN % 32 == 0, "whole 32x32 blocks");
@@ -103,12 +105,15 @@ __global__ __launch_bounds__(256) void conv_gather_dma_kernel(GatherConvArgs a, 
     }
   }
   const char* zero = reinterpret_cast<const char*>(g_zero_word);
-  const int cpc = a.Ci >> 6;              // chunks per tap
+  const int cpc = (a.Ci + 63) >> 6;       // chunks per tap
   const int nchunks = b.ntaps * cpc;
+  // the k-unit this lane loads is the same for all its rows: (row >> 1) & 7 = (4 * (wave & 1) + (lane >> 4)) & 7
+  const int ku = (lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7);
 
   auto issue = [&](int kc) {
     unsigned char* stage = smem + (size_t)(kc % STAGES) * (R * ROWB);
     const int tapi = kc / cpc, cb = (kc - tapi * cpc) * 128;   // byte offset of the 64-channel block
+    const bool kv = !KTAIL || (cb >> 1) + ku * 8 < a.Ci;       // this lane's 8 channels exist
     const int tp = a.nclass > 1 ? a.ctap[cls][tapi] : a.tap[tapi];
     const int dh = (tp & 0xff) - 8, dw = ((tp >> 8) & 0xff) - 8, kofs = tp >> 16;
     const long xoff = ((long)dh * a.Wi + dw) * a.Ci * 2 + cb;
@@ -118,9 +123,9 @@ __global__ __launch_bounds__(256) void conv_gather_dma_kernel(GatherConvArgs a, 
       const char* g;
       if (j < JX) {
         const int ih = (hw[j] >> 16) + dh, iw = (hw[j] & 0xffff) + dw;
-        g = ((unsigned)ih < (unsigned)a.Hi && (unsigned)iw < (unsigned)a.Wi) ? src[j] + xoff : zero;
+        g = ((unsigned)ih < (unsigned)a.Hi && (unsigned)iw < (unsigned)a.Wi && kv) ? src[j] + xoff : zero;
       } else {
-        g = wok[j - JX] ? src[j] + woff : zero;
+        g = (wok[j - JX] && kv) ? src[j] + woff : zero;
       }
       dma16(g, stage + (size_t)(8 * (4 * j + wave)) * ROWB);
     }
@@ -465,6 +470,7 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
 
 // the patch form needs: nine taps within +-1, unit strides, coinciding input and output grids
 static bool conv_patch_applies(const GatherConvArgs& a) {
+  if (a.Ci % 64 != 0) return false;
   if (a.ntaps != 9 || a.in_stride != 1 || a.out_stride != 1 || a.ooh != 0 || a.oow != 0) return false;
   if (a.OH != a.Hi || a.OW != a.Wi || a.OHf != a.OH || a.OWf != a.OW || a.Wi > 32 || a.Wi < 1) return false;
   if (a.w_rows != a.Co) return false;                                     // no rows of zeros inside the weight matrix
@@ -506,22 +512,24 @@ static hipError_t run_patch_rows(const GatherConvArgs& a, hipStream_t s) {
 }
 
 bool conv_gather_wide_applies(const GatherConvArgs& a) {
-  return a.Ci % 64 == 0 && a.Co >= 128 && a.ntaps >= 1 && a.Kw % 8 == 0 && a.Hi < 32768 && a.Wi < 32768;
+  // input channels: whole 64-channel chunks, or at least two chunks with a partly filled last one (160 = 2.5 chunks)
+  const bool k_ok = a.Ci % 64 == 0 || (a.Ci % 8 == 0 && a.Ci >= 128);
+  return k_ok && a.Co >= 128 && a.ntaps >= 1 && a.Kw % 8 == 0 && a.Hi < 32768 && a.Wi < 32768;
 }
 
-template <int BN, int STAGES>
-static hipError_t run_wide(const GatherConvArgs& a, hipStream_t s) {
+template <int BN, int STAGES, bool KTAIL>
+static hipError_t run_wide_k(const GatherConvArgs& a, hipStream_t s) {
   constexpr size_t lds = (size_t)STAGES * (128 + BN) * 128;
   static bool configured = false;   // one attribute call per instantiation (idempotent, so a race is harmless)
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_gather_dma_kernel<BN, STAGES>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_gather_dma_kernel<BN, STAGES, KTAIL>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     configured = true;
   }
   const int n_tiles = (a.Co + BN - 1) / BN;
   static char name[64];
-  if (!name[0]) snprintf(name, sizeof(name), "conv_gather_dma_kernel<%d, %d>", BN, STAGES);
+  if (!name[0]) snprintf(name, sizeof(name), "conv_gather_dma_kernel<%d, %d, %s>", BN, STAGES, KTAIL ? "true" : "false");
   note_kernel(name);
   if (a.nclass > 1) {
     GatherConvArgs m = a;
@@ -532,18 +540,23 @@ static hipError_t run_wide(const GatherConvArgs& a, hipStream_t s) {
     }
     m.cls_start[a.nclass] = tiles;
     if (tiles <= 0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((conv_gather_dma_kernel<BN, STAGES>), dim3(tiles), dim3(256), lds, s, m, 0, n_tiles);
+    hipLaunchKernelGGL((conv_gather_dma_kernel<BN, STAGES, KTAIL>), dim3(tiles), dim3(256), lds, s, m, 0, n_tiles);
     return hipGetLastError();
   }
   const int Mtot = a.N * a.OH * a.OW;
   const int m_tiles = (Mtot + 127) / 128;
-  hipLaunchKernelGGL((conv_gather_dma_kernel<BN, STAGES>), dim3(m_tiles * n_tiles), dim3(256), lds, s, a, m_tiles, n_tiles);
+  hipLaunchKernelGGL((conv_gather_dma_kernel<BN, STAGES, KTAIL>), dim3(m_tiles * n_tiles), dim3(256), lds, s, a, m_tiles, n_tiles);
   return hipGetLastError();
+}
+
+template <int BN, int STAGES>
+static hipError_t run_wide(const GatherConvArgs& a, hipStream_t s) {
+  return a.Ci % 64 == 0 ? run_wide_k<BN, STAGES, false>(a, s) : run_wide_k<BN, STAGES, true>(a, s);
 }
 
 hipError_t launch_conv_gather_wide(const GatherConvArgs& a, hipStream_t s) {
   if (a.nclass > 1) {   // the caller has checked conv_gather_wide_applies on the common fields
-    if (a.nclass > 4 || a.Ci % 64 != 0 || a.Co < 128) return hipErrorInvalidValue;
+    if (a.nclass > 4 || a.Ci % 8 != 0 || a.Ci < 64 || a.Co < 128) return hipErrorInvalidValue;
     return a.Co % 160 == 0 ? run_wide<160, 4>(a, s) : run_wide<128, 4>(a, s);
   }
   if (!conv_gather_wide_applies(a) || a.N * a.OH * a.OW <= 0) return hipErrorInvalidValue;

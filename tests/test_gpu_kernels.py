@@ -68,6 +68,8 @@ CONV_CASES = [  # n, h, w, ci, co, ksize, stride
     (2, 8, 8, 320, 640, 1, 2),
     (5, 4, 4, 128, 192, 1, 1),
     (16, 8, 8, 640, 640, 3, 1),
+    (3, 6, 6, 136, 128, 3, 1),      # input channels = 2 chunks of 64 + 8: the partly filled last chunk
+    (2, 8, 8, 200, 160, 1, 2),
     # channel counts that are multiples of 160: the transposing direct-to-LDS weight-gradient kernel
     (3, 4, 4, 160, 160, 3, 1),
     (5, 8, 8, 160, 320, 3, 1),
@@ -153,6 +155,8 @@ GATED_CASES = [  # data gradients the wide kernels run: output (= layer input) c
     (3, 9, 7, 192, 320, 3, 2),      # four parity classes, odd sizes
     (2, 8, 8, 320, 640, 1, 2),      # three of the four classes have no tap: zeros (plus addend) gated
     (5, 4, 4, 128, 192, 1, 1),
+    (2, 8, 8, 160, 160, 3, 1),      # contraction over 160 channels: a partly filled last 64-channel chunk
+    (2, 8, 8, 160, 136, 3, 2),      # the same with parity classes (136 = 2 chunks + 8 channels)
 ]
 
 
