@@ -1056,6 +1056,257 @@ __global__ __launch_bounds__(256) void conv_wgrad128_kernel(WgradArgs a, Wgrad12
   }
 }
 
+// The same 128 x 128 blocks with EIGHT waves, two per SIMD.  Four waves issue the direct-to-LDS loads, the LDS reads
+// and the MFMAs of a step one after the other and end up at the sum of the three times; LDS reads of four waves also
+// top out near 80 bytes per clock against 150 with eight.  Here wave (wm, wn, wk) owns 64 output channels x 64 input
+// channels (2 x 2 accumulator blocks: 64 registers, so two waves fit a SIMD easily) and two of the four 16-pixel
+// steps of every 64-pixel chunk; while one wave of a SIMD waits for its reads or for the load queue, the other
+// one's MFMAs run.  Fragments are double buffered (a step's reads are issued during the step before it, two per
+// MFMA slot), next-chunk / still-loading are compile-time tags, load addresses are 32-bit offsets from two
+// uniform pointers that advance with the chunk.
+template <int STAGES>
+__global__ __launch_bounds__(512) void conv_wgrad128w8_kernel(WgradArgs a, Wgrad128Launch L) {
+  constexpr int BC = 128, BKP = 64, ROWB = BC * 2, PART = BKP * ROWB, STAGE = 2 * PART, NT = 512, NW = NT / 64;
+  constexpr int JP = BKP * (BC / 8) / NT, NJ = 2 * JP;   // loads per thread, chunk and operand: 2
+  constexpr int NM = 4;                                  // MFMAs per wave and 16-pixel step
+  static_assert(STAGES >= 3 && (STAGES - 2) * NJ < 64, "pipeline depth / vmcnt range");
+  static_assert(STAGES * STAGE >= NW * 2 * 4096, "room for the exchange of the partial blocks");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // STAGES * STAGE
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave & 1, wn = (wave >> 1) & 1, wk = wave >> 2;
+
+  int t = xcd_consecutive(blockIdx.x, gridDim.x);   // see conv_wgrad128_kernel
+  const int tapi = t % a.ntaps; t /= a.ntaps;
+  const int ci_t = t % L.ci_tiles; t /= L.ci_tiles;
+  const int co_t = t % L.co_tiles;
+  const int split = t / L.co_tiles;
+  const int co0 = co_t * BC, ci0 = ci_t * BC;
+  const int tp = a.tap[tapi];
+  const int dh = (tp & 0xff) - 8, dw = ((tp >> 8) & 0xff) - 8;
+  const int total_chunks = (a.N * a.OH * a.OW) / BKP;
+  const int chunk_lo = split * L.chunks_per_split;
+  const int n = min(total_chunks, chunk_lo + L.chunks_per_split) - chunk_lo;
+  if (n <= 0) return;
+
+  // ---- per-thread DMA sources: 32-bit byte offsets from two uniform pointers that advance with the chunk.  The x
+  //      pointer starts one input row and one pixel before the chunk's first pixel, so that the offsets of taps
+  //      that reach backwards stay non-negative (rows outside the image are never loaded) ----
+  const int m0 = chunk_lo * BKP;
+  const int oh0 = (m0 / a.OW) % a.OH, n0 = m0 / (a.OW * a.OH);    // BKP % OW == 0: m0 starts an output row
+  const long long xrow0 = (long long)n0 * a.Hi + oh0 * a.stride;
+  const int margin = (a.Wi + 1) * a.Cx * 2;
+  const char* a_next = reinterpret_cast<const char*>(a.dy) + (size_t)m0 * a.Co * 2;
+  const char* b_next = reinterpret_cast<const char*>(a.x) + xrow0 * a.Wi * a.Cx * 2 - margin;
+  unsigned aoff32[JP], boff32[JP], bmask[JP];
+#pragma unroll
+  for (int j = 0; j < JP; ++j) {
+    const int P = 64 * (NW * j + wave) + lane;
+    const int r = P >> 4, up = P & 15;
+    const int u = 2 * ((up >> 1) ^ (2 * (r & 3))) + (up & 1);           // 256-byte rows: slot ^ 2 * (pixel & 3)
+    aoff32[j] = (unsigned)((r * a.Co + co0 + u * 8) * 2);
+    const int ow = r % a.OW, orow = r / a.OW;
+    const int iw = ow * a.stride + dw;
+    const bool colok = (unsigned)iw < (unsigned)a.Wi;
+    boff32[j] = (unsigned)(margin + (((orow * a.stride + dh) * a.Wi + iw) * a.Cx + ci0 + u * 8) * 2);
+    unsigned mask = 0;
+    int ohq = (oh0 + orow) % a.OH;
+    for (int q = 0; q < L.period; ++q) {
+      if (colok && (unsigned)(ohq * a.stride + dh) < (unsigned)a.Hi) mask |= 1u << q;
+      ohq += L.d_oh;
+      if (ohq >= a.OH) ohq -= a.OH;
+    }
+    bmask[j] = mask;
+  }
+  const uint64_t zero_addr = (uint64_t)g_zero_word;
+  uint32_t zero_lo = (uint32_t)zero_addr, zero_hi = (uint32_t)(zero_addr >> 32);
+  asm volatile("" : "+s"(zero_lo), "+s"(zero_hi));   // kept in two registers (rebuilt from the program counter otherwise)
+
+  const unsigned lds0 = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)smem);
+  unsigned phase_bit = 1u;                 // 1 << ((chunk being issued) mod period)
+  const unsigned last_phase_bit = 1u << (L.period - 1);
+  unsigned issue_stage = 0;                // LDS byte offset of the stage being filled
+  auto issue_one = [&](int d) {
+    unsigned char* stage = smem + issue_stage;
+    if (d < JP) {
+      dma16(a_next + aoff32[d], stage + (64 * (NW * d + wave)) * 16);
+    } else {
+      const int j = d - JP;
+      const bool ok = (bmask[j] & phase_bit) != 0;
+      const uint64_t pa = (uint64_t)(b_next + boff32[j]);
+      const uint32_t lo = ok ? (uint32_t)pa : zero_lo, hi = ok ? (uint32_t)(pa >> 32) : zero_hi;
+      dma16((const char*)(((uint64_t)hi << 32) | lo), stage + PART + (64 * (NW * j + wave)) * 16);
+    }
+  };
+  auto issue_done = [&]() {
+    phase_bit = phase_bit == last_phase_bit ? 1u : phase_bit << 1;
+    issue_stage = issue_stage == (STAGES - 1) * STAGE ? 0u : issue_stage + STAGE;
+    a_next += L.a_step;
+    b_next += L.b_step;
+  };
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // ---- operand reads: lane group g = lane >> 4 takes channels 16*(g&1).. of a 32-channel block and pixels
+  //      8*(g>>1) .. +7 of a 16-pixel step (two transposing reads of 4 pixels each); this wave's steps are
+  //      2 wk and 2 wk + 1 of the chunk ----
+  unsigned foff[4];   // 0, 1: dy blocks 2 wm, 2 wm + 1;  2, 3: x blocks 2 wn, 2 wn + 1
+  {
+    const int g = lane >> 4, i16 = lane & 15;
+    const int prow = 32 * wk + 8 * (g >> 1) + (i16 >> 2);
+    const int x = 2 * ((i16 >> 2) & 3);
+#pragma unroll
+    for (int f = 0; f < 2; ++f) {
+      foff[f] = lds0 + prow * ROWB + (i16 & 3) * 8 + (((2 * (2 * wm + f) + (g & 1)) ^ x) * 32);
+      foff[2 + f] = lds0 + PART + prow * ROWB + (i16 & 3) * 8 + (((2 * (2 * wn + f) + (g & 1)) ^ x) * 32);
+    }
+  }
+  // fragment index by position in read order = the order the MFMAs (K = 2 i + j) first need them: A0 B0 B1 A1
+  v4s16 flo[2][4], fhi[2][4];   // [set][fragment]: fragment 0, 1 = dy; 2, 3 = x
+  auto read_pos = [&](auto set_tag, auto pos_tag, unsigned stage_off, auto ks_tag) {
+    constexpr int S = decltype(set_tag)::value, POS = decltype(pos_tag)::value, KS = decltype(ks_tag)::value;
+    constexpr int F = POS == 0 ? 0 : (POS == 1 ? 2 : (POS == 2 ? 3 : 1));
+    const unsigned addr = foff[F] + stage_off;
+    v4s16 &lo = flo[S][F], &hi = fhi[S][F];
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(addr), "i"((KS * 16) * ROWB));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "i"((KS * 16 + 4) * ROWB));
+  };
+  auto wait_frag = [&](auto set_tag, auto f_tag, auto n_tag) {   // fragment F has landed when at most N reads are outstanding
+    constexpr int S = decltype(set_tag)::value, F = decltype(f_tag)::value, N = decltype(n_tag)::value;
+    static_assert(N >= 0 && N <= 15, "lgkmcnt range");
+    v4s16 &lo = flo[S][F], &hi = fhi[S][F];
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(lo), "+v"(hi) : "n"(N));
+  };
+  auto frag = [&](auto set_tag, int f) {
+    constexpr int S = decltype(set_tag)::value;
+    typedef short v8s16 __attribute__((ext_vector_type(8)));
+    const v8s16 both = __builtin_shufflevector(flo[S][f], fhi[S][f], 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, both);
+  };
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>;
+  using I3 = std::integral_constant<int, 3>;
+
+  // prologue: chunks 0 .. STAGES-2 in flight, chunk 0 visible, the fragments of its first step read
+#pragma unroll
+  for (int p = 0; p < STAGES - 1; ++p)
+    if (p < n) {
+#pragma unroll
+      for (int d = 0; d < NJ; ++d) issue_one(d);
+      issue_done();
+    }
+  static_for<STAGES - 1>([&](auto q_tag) {
+    constexpr int Q = decltype(q_tag)::value;   // chunks issued after chunk 0
+    if ((n < STAGES - 1 ? n : STAGES - 1) - 1 == Q) wait_vmcnt<Q * NJ>();
+  });
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  static_for<4>([&](auto pos) { read_pos(I0{}, pos, 0u, I0{}); });
+
+  // One 16-pixel step = 4 (MFMA, piece) slots on fragment set KS.  Pieces: after MFMA k the two reads of fragment
+  // position k of the following step into the other set (`more`: there is a following step); after slot 1 of a
+  // chunk's first step the barrier that makes the next chunk visible (`bar`); one load of chunk c+STAGES-1 in
+  // slots 2, 3 of the first step and 0, 1 of the second (`issue`).
+  unsigned rd_stage = 0;   // LDS byte offset of the stage of chunk c
+  auto step = [&](auto ks_tag, auto more_tag, auto bar_tag, auto issue_tag, unsigned next_stage) {
+    constexpr int KS = decltype(ks_tag)::value;
+    constexpr bool more = decltype(more_tag)::value, bar = decltype(bar_tag)::value, issue = decltype(issue_tag)::value;
+    using set = std::integral_constant<int, KS>;
+    using other = std::integral_constant<int, 1 - KS>;
+    const unsigned rd = KS == 0 ? rd_stage : next_stage;   // where the following step's operands are
+    static_for<NM>([&](auto k) {
+      constexpr int K = decltype(k)::value;
+      // this step's reads went out in the order A0 B0 B1 A1, two each; K newer pairs follow them by now
+      if constexpr (K == 0) {
+        wait_frag(set{}, I0{}, std::integral_constant<int, 6>{});
+        wait_frag(set{}, I2{}, std::integral_constant<int, 4>{});
+      } else if constexpr (K == 1) {
+        wait_frag(set{}, I3{}, std::integral_constant<int, more ? 4 : 2>{});
+      } else if constexpr (K == 2) {
+        wait_frag(set{}, I1{}, std::integral_constant<int, more ? 4 : 0>{});
+      }
+      acc[K >> 1][K & 1] = mfma32(frag(set{}, K >> 1), frag(set{}, 2 + (K & 1)), acc[K >> 1][K & 1]);
+      if constexpr (more) read_pos(other{}, k, rd, other{});
+      if constexpr (bar && K == 1) {
+        if constexpr (issue) wait_vmcnt<(STAGES - 3) * NJ>(); else wait_vmcnt<0>();
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+      }
+      if constexpr (issue) {
+        if constexpr (KS == 0 && K >= 2) issue_one(K - 2);
+        if constexpr (KS == 1 && K < 2) issue_one(K + 2);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+  };
+  auto chunk = [&](auto next_tag, auto issue_tag) {
+    const unsigned next_stage = rd_stage == (STAGES - 1) * STAGE ? 0u : rd_stage + STAGE;
+    step(I0{}, std::true_type{}, next_tag, issue_tag, next_stage);
+    step(I1{}, next_tag, std::false_type{}, issue_tag, next_stage);
+    if constexpr (decltype(issue_tag)::value) issue_done();
+    rd_stage = next_stage;
+  };
+  {
+    using yes = std::true_type;
+    using no = std::false_type;
+    int c = 0;
+    for (; c + STAGES - 1 < n; ++c) chunk(yes{}, yes{});
+    for (; c + 1 < n; ++c) chunk(yes{}, no{});
+    if (c < n) chunk(no{}, no{});
+  }
+
+  // ---- add the two pixel halves: wave (wm, wn, wk) keeps block row wk of its two and receives its partner's ----
+  wait_vmcnt<0>();
+  __syncthreads();
+  f32x4* mine = reinterpret_cast<f32x4*>(smem) + (size_t)wave * 512;
+  const f32x4* theirs = reinterpret_cast<const f32x4*>(smem) + (size_t)(wave ^ 4) * 512;
+  f32x16 keep[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const f32x16 give = wk == 0 ? acc[1][j] : acc[0][j];
+    keep[j] = wk == 0 ? acc[0][j] : acc[1][j];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      mine[(j * 4 + g) * 64 + lane] = f32x4{give[4 * g], give[4 * g + 1], give[4 * g + 2], give[4 * g + 3]};
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const f32x4 p = theirs[(j * 4 + g) * 64 + lane];
+      keep[j][4 * g] += p[0]; keep[j][4 * g + 1] += p[1]; keep[j][4 * g + 2] += p[2]; keep[j][4 * g + 3] += p[3];
+    }
+  // D block: lane holds column ci = 32 j + (lane & 31), rows co = 8 (v >> 2) + 4 (lane >> 5) + (v & 3) of the block row
+  float* dst = L.partial ? L.partial + (size_t)split * L.split_stride : a.dw;
+  const int mode = (L.partial || (L.splits == 1 && a.overwrite)) ? 0 : (L.splits > 1 ? 1 : 2);
+  const int ntaps = a.ntaps, Ci = a.Ci;
+  const int co_base = co0 + 64 * wm + 32 * wk + 4 * (lane >> 5);
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int ci = ci0 + 64 * wn + 32 * j + (lane & 31);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int co = co_base + 8 * (v >> 2) + (v & 3);
+      float* o = dst + ((size_t)co * ntaps + tapi) * Ci + ci;
+      const float val = keep[j][v];
+      if (mode == 0) *o = val;
+      else if (mode == 1) atomicAdd(o, val);
+      else *o += val;
+    }
+  }
+}
+
 bool conv_wgrad128_applies(const WgradArgs& a) {
   if (a.Co % 128 != 0 || a.Ci % 128 != 0 || a.Cx != a.Ci || a.ntaps < 1) return false;
   if (a.OW < 1 || 64 % a.OW != 0 || (a.N * a.OH * a.OW) % 64 != 0 || a.OH > 32) return false;
@@ -1099,8 +1350,21 @@ hipError_t launch_conv_wgrad128(const WgradArgs& a, hipStream_t s) {
   L.period = a.OH / g;
   L.a_step = (long long)64 * a.Co * 2;
   L.b_step = (long long)d_oh_full * a.stride * a.Wi * a.Cx * 2;
+  static const bool four_waves = getenv("FDG_WGRAD_4W") != nullptr;   // A/B switch for measurements
+  if (!four_waves) {
+    static bool configured8 = false;
+    if (!configured8) {
+      hipError_t e8 = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad128w8_kernel<STAGES>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e8 != hipSuccess) return e8;
+      configured8 = true;
+    }
+    note_kernel("conv_wgrad128w8_kernel<5>");
+    hipLaunchKernelGGL((conv_wgrad128w8_kernel<STAGES>), dim3(tiles * L.splits), dim3(512), lds, s, a, L);
+  } else {
   note_kernel("conv_wgrad128_kernel<5>");
   hipLaunchKernelGGL((conv_wgrad128_kernel<STAGES>), dim3(tiles * L.splits), dim3(256), lds, s, a, L);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || !L.partial) return e;
   const size_t n4 = elems / 4;
