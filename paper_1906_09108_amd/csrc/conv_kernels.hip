@@ -12,6 +12,7 @@
 // MFMA operand layout used throughout (16x16x32, 64 lanes): lane l supplies row (l & 15) of A and
 // column (l & 15) of B, each with the 8 consecutive k values 8*(l >> 4) .. +7; lane l receives
 // D[4*(l >> 4) + v][l & 15] in accumulator component v.
+#include <algorithm>
 #include "conv_common.h"
 #include <stdio.h>
 #include <stdlib.h>
@@ -476,7 +477,15 @@ size_t conv_wgrad_scratch_bytes(const ConvShape& c) {
   WgradArgs a{};
   a.Co = c.Co; a.Ci = c.Ci; a.Cx = c.Cip; a.OW = c.Wo(); a.ntaps = c.T;
   a.N = c.N; a.OH = c.Ho(); a.Hi = c.Hi; a.Wi = c.Wi; a.stride = c.stride;
-  return (conv_wgrad_wide_applies(a) || conv_wgrad128_applies(a) || conv_wgrad_tall_applies(a)) ? (size_t)8 * c.Co * c.T * c.Ci * 4 : 0;
+  if (!(conv_wgrad_wide_applies(a) || conv_wgrad128_applies(a) || conv_wgrad_tall_applies(a))) return 0;
+  // room for the partial sums of the pixel splits: 8 of them, or as many as it takes the 160 x 160 kernel to fill
+  // the chip when a layer has few blocks (160 -> 160: 9 blocks per filter)
+  size_t splits = 8;
+  if (!conv_wgrad128_applies(a) && !conv_wgrad_tall_applies(a)) {
+    const size_t tiles = (size_t)(c.Co / 160) * (c.Ci / 160) * c.T;
+    splits = std::min<size_t>(32, std::max<size_t>(8, (256 + tiles - 1) / tiles));
+  }
+  return splits * c.Co * c.T * c.Ci * 4;
 }
 
 hipError_t conv_wgrad(const ConvShape& c, const bf16_t* x, const bf16_t* dy, float* dw, float* scratch,

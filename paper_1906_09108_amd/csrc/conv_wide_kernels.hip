@@ -1748,7 +1748,7 @@ hipError_t launch_conv_wgrad_wide(const WgradArgs& a, hipStream_t s) {
   int best = 1;
   if (max_by_scratch >= 2) {
     double best_cost = 1e30;
-    for (int S = 1; S <= 8 && S <= max_by_scratch && S <= total_chunks; ++S) {
+    for (int S = 1; S <= 32 && S <= max_by_scratch && S <= total_chunks; ++S) {
       const int rounds = (tiles * S + 255) / 256, cps = (total_chunks + S - 1) / S;
       const double cost = (double)rounds * cps * 1.0 + (S > 1 ? (2.0 * S + 2.0) * elems * 4 / 3.0e6 : 0.0);
       if (cost < best_cost) { best_cost = cost; best = S; }
