@@ -204,7 +204,10 @@ __device__ __forceinline__ void static_for(F&& f) {
   static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
-template <int BN, int PR, int WS>
+// KTAIL: the input channels are not a multiple of 64 (WRN's 160).  The last channel block is then partly beyond the
+// tensor: its 16-byte units past the last channel are loaded from the zero word, for the patch and the weights alike,
+// which costs every load of such a layer a per-lane address select (the other layers keep the uniform-base form).
+template <int BN, int PR, int WS, bool KTAIL>
 __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m_tiles, int n_tiles) {
   constexpr int BM = 128, ROWB = 128;
   static_assert(BN % 32 == 0 && PR % 32 == 0, "whole DMA instructions and 32x32 blocks");
@@ -254,15 +257,53 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
   int tko[9];
 #pragma unroll
   for (int i = 0; i < 9; ++i) tko[i] = (a.tap[i] >> 16) * a.Ci * 2;   // byte offset of the tap's k block in a weight row
-  const int cpc = a.Ci >> 6;   // channel blocks
+  const int cpc = (a.Ci + 63) >> 6;   // channel blocks
+  // KTAIL: bit j (patch loads) / bit 16 + j (weight loads): this lane's unit exists in the last channel block
+  unsigned tail_ok = 0;
+  uint32_t zero_lo = 0, zero_hi = 0;
+  if (KTAIL) {
+#pragma unroll
+    for (int j = 0; j < JX; ++j) {
+      const int p = 8 * (4 * j + wave) + (lane >> 3);
+      const int u = (lane & 7) ^ ((p >> 1) & 7);
+      if ((cpc - 1) * 64 + u * 8 < a.Ci) tail_ok |= 1u << j;
+    }
+#pragma unroll
+    for (int j = 0; j < JW; ++j) {
+      const int row = 8 * (4 * j + wave) + (lane >> 3);
+      const int u = (lane & 7) ^ ((row >> 1) & 7);
+      if ((cpc - 1) * 64 + u * 8 < a.Ci) tail_ok |= 1u << (16 + j);
+    }
+    const uint64_t z = (uint64_t)g_zero_word;
+    zero_lo = (uint32_t)z; zero_hi = (uint32_t)(z >> 32);
+    asm volatile("" : "+v"(zero_lo), "+v"(zero_hi));
+  }
+  static_assert(JX <= 16 && JW <= 16, "bits of tail_ok");
 
   auto issue_x_one = [&](int j, int c) {
     const char* base = reinterpret_cast<const char*>(a.in) + (size_t)c * 128;
-    dma16(base + (size_t)xoff[j], smem + (c & 1) * XBYTES + (8 * (4 * j + wave)) * ROWB);
+    unsigned char* dst = smem + (c & 1) * XBYTES + (8 * (4 * j + wave)) * ROWB;
+    if (KTAIL) {
+      const bool ok = c != cpc - 1 || ((tail_ok >> j) & 1u);
+      const uint64_t pa = (uint64_t)(base + (size_t)xoff[j]);
+      const uint32_t lo = ok ? (uint32_t)pa : zero_lo, hi = ok ? (uint32_t)(pa >> 32) : zero_hi;
+      dma16((const char*)(((uint64_t)hi << 32) | lo), dst);
+    } else {
+      dma16(base + (size_t)xoff[j], dst);
+    }
   };
-  auto issue_w_one = [&](int j, int slot, int kbyte) {
+  // cblock: the channel block the weights belong to
+  auto issue_w_one = [&](int j, int slot, int kbyte, int cblock) {
     const char* base = reinterpret_cast<const char*>(a.w) + (size_t)kbyte;
-    dma16(base + (size_t)woff[j], smem + 2 * XBYTES + slot * WBYTES + (8 * (4 * j + wave)) * ROWB);
+    unsigned char* dst = smem + 2 * XBYTES + slot * WBYTES + (8 * (4 * j + wave)) * ROWB;
+    if (KTAIL) {
+      const bool ok = cblock != cpc - 1 || ((tail_ok >> (16 + j)) & 1u);
+      const uint64_t pa = (uint64_t)(base + (size_t)woff[j]);
+      const uint32_t lo = ok ? (uint32_t)pa : zero_lo, hi = ok ? (uint32_t)(pa >> 32) : zero_hi;
+      dma16((const char*)(((uint64_t)hi << 32) | lo), dst);
+    } else {
+      dma16(base + (size_t)woff[j], dst);
+    }
   };
   // the first loads go out before the rest of the set-up, which then runs while they are in flight
 #pragma unroll
@@ -270,7 +311,7 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
 #pragma unroll
   for (int p = 0; p < WS - 1; ++p)   // 9 taps >= WS - 1 steps always exist
 #pragma unroll
-    for (int j = 0; j < JW; ++j) issue_w_one(j, p, tko[p]);
+    for (int j = 0; j < JW; ++j) issue_w_one(j, p, tko[p], 0);
 
   f32x16 acc[FN][FM];
 #pragma unroll
@@ -412,12 +453,13 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
       constexpr int NW = ISSUE_W ? JW : 0;
       constexpr int NX = gsize(T, LAST) - NW;             // patch loads of this group: pieces T*PER ...
       const int kbyte = TT < 9 ? tko[TT < 9 ? TT : 0] + c * 128 : tko[TT < 9 ? 0 : TT - 9] + (c + 1) * 128;
+      const int wblock = TT < 9 ? c : c + 1;
       // load idx of the group goes out after the MFMA of global slot 3 + 2 idx (slots 0 .. 2 NM - 1 over both halves)
       auto issue_at = [&](auto s_tag) {
         constexpr int SL = decltype(s_tag)::value;
         if constexpr (SL >= 3 && (SL - 3) % 2 == 0) {
           constexpr int IDX = (SL - 3) / 2;
-          if constexpr (IDX < NW) issue_w_one(IDX, islot, kbyte);
+          if constexpr (IDX < NW) issue_w_one(IDX, islot, kbyte, wblock);
           else if constexpr (IDX - NW < NX) issue_x_one(T * PER + IDX - NW, c + 1);
         }
       };
@@ -470,7 +512,7 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
 
 // the patch form needs: nine taps within +-1, unit strides, coinciding input and output grids
 static bool conv_patch_applies(const GatherConvArgs& a) {
-  if (a.Ci % 64 != 0) return false;
+  if (a.Ci % 64 != 0 && (a.Ci % 8 != 0 || a.Ci < 128)) return false;   // whole channel blocks, or >= 2 with a partly filled last one
   if (a.ntaps != 9 || a.in_stride != 1 || a.out_stride != 1 || a.ooh != 0 || a.oow != 0) return false;
   if (a.OH != a.Hi || a.OW != a.Wi || a.OHf != a.OH || a.OWf != a.OW || a.Wi > 32 || a.Wi < 1) return false;
   if (a.w_rows != a.Co) return false;                                     // no rows of zeros inside the weight matrix
@@ -482,14 +524,14 @@ static bool conv_patch_applies(const GatherConvArgs& a) {
   return true;
 }
 
-template <int BN, int PR>
-static hipError_t run_patch(const GatherConvArgs& a, hipStream_t s) {
+template <int BN, int PR, bool KTAIL>
+static hipError_t run_patch_k(const GatherConvArgs& a, hipStream_t s) {
   constexpr int WS = 5;
   constexpr size_t lds = (size_t)2 * (PR * 128 + 256) + (size_t)WS * BN * 128;
   static_assert(lds + 2 * BN * 4 <= 160 * 1024, "LDS of one compute unit");
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_patch_kernel<BN, PR, WS>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_patch_kernel<BN, PR, WS, KTAIL>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     configured = true;
@@ -497,10 +539,15 @@ static hipError_t run_patch(const GatherConvArgs& a, hipStream_t s) {
   const int Mtot = a.N * a.OH * a.OW;
   const int m_tiles = (Mtot + 127) / 128, n_tiles = (a.Co + BN - 1) / BN;
   static char name[64];
-  if (!name[0]) snprintf(name, sizeof(name), "conv_patch_kernel<%d, %d, %d>", BN, PR, WS);
+  if (!name[0]) snprintf(name, sizeof(name), KTAIL ? "conv_patch_kernel<%d, %d, %d, true>" : "conv_patch_kernel<%d, %d, %d>", BN, PR, WS);
   note_kernel(name);
-  hipLaunchKernelGGL((conv_patch_kernel<BN, PR, WS>), dim3(m_tiles * n_tiles), dim3(256), lds, s, a, m_tiles, n_tiles);
+  hipLaunchKernelGGL((conv_patch_kernel<BN, PR, WS, KTAIL>), dim3(m_tiles * n_tiles), dim3(256), lds, s, a, m_tiles, n_tiles);
   return hipGetLastError();
+}
+
+template <int BN, int PR>
+static hipError_t run_patch(const GatherConvArgs& a, hipStream_t s) {
+  return a.Ci % 64 == 0 ? run_patch_k<BN, PR, false>(a, s) : run_patch_k<BN, PR, true>(a, s);
 }
 
 template <int BN>
