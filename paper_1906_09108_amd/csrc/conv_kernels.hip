@@ -350,6 +350,7 @@ hipError_t launch_conv_wgrad(const WgradArgs& a, hipStream_t s) {
     if (e != hipSuccess) return e;
   }
   if (a.Co <= 64 && a.Cx <= 64) return run_wgrad<32, 32, 1, 1, 4>(a, s);
+  if (a.Cx <= 32) return run_wgrad<128, 32, 4, 1, 1>(a, s);   // many output channels from few inputs (WRN's 16 -> 160)
   return run_wgrad<128, 128, 2, 2, 1>(a, s);
 }
 

@@ -60,6 +60,8 @@ CONV_CASES = [  # n, h, w, ci, co, ksize, stride
     (8, 8, 8, 320, 320, 3, 1),
     (4, 16, 16, 160, 320, 3, 2),
     (16, 32, 32, 16, 16, 3, 1),
+    (4, 16, 16, 16, 160, 3, 1),     # many output channels from few inputs: the 128 x 32 weight-gradient tiles
+    (2, 9, 9, 24, 136, 1, 1),
     # wide layers (input channels a multiple of 64): the direct-to-LDS kernel, both tile widths, ragged pixels
     (2, 8, 8, 64, 160, 3, 1),
     (3, 7, 5, 128, 128, 3, 1),
