@@ -122,15 +122,19 @@ constexpr int out_stage_bytes(int BN) { return 32 * out_stage_pitch(BN) + 128; }
 // where the lanes park their partial statistics: 4 waves x PERIOD x 64 lanes x 8 floats (PERIOD = 5 for 160 channels)
 constexpr int stats_stage_bytes(int BN) { return 4 * ((BN / 4) % 16 == 0 ? 1 : (BN / 4) / 8) * 64 * 32; }
 
-template <int FN, int BN>
+// Kernels with eight waves (256 registers, 8 regions in the LDS) turn the block ROWS = 16 pixels at a time, issue the
+// loads of GROUP = 5 iterations together (about 14 registers per iteration) and park the statistics of PARKW = 8
+// waves where the regions were (stats_lds may then overlap them: a barrier separates the two uses).
+template <int FN, int BN, int GROUP = 10, int ROWS = 32, int PARKW = 4>
 __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x16 (&acc)[FN], int m_base, int c_tile,
                                              int lane, unsigned char* lds, unsigned char* stats_lds) {
   static_assert(FN * 32 == BN, "one wave carries all channels of the tile");
+  static_assert(ROWS == 32 || ROWS == 16, "whole or half blocks");
   constexpr int PITCH = out_stage_pitch(BN);
   constexpr int UNITS = BN / 4;                       // 16-byte fp32 units per pixel
-  constexpr int ITERS = 32 * UNITS / 64;
+  constexpr int ITERS = ROWS * UNITS / 64;
   constexpr int PERIOD = UNITS % 64 == 0 ? 1 : (UNITS % 32 == 0 ? 1 : (UNITS % 16 == 0 ? UNITS / 16 : (UNITS % 8 == 0 ? UNITS / 8 : UNITS)));
-  static_assert((64 * PERIOD) % UNITS == 0 && ITERS % PERIOD == 0, "unit assignment repeats every PERIOD iterations");
+  static_assert((64 * PERIOD) % UNITS == 0 && ITERS % PERIOD == 0 && (ROWS * UNITS) % 64 == 0, "unit assignment repeats every PERIOD iterations");
   static_assert(stats_stage_bytes(BN) == 4 * PERIOD * 64 * 32, "size of the statistics stage");
   const int Mtot = a.N * a.OH * a.OW;
   // The arguments live in constant memory, and a compiler short of scalar registers re-reads them at every
@@ -146,34 +150,38 @@ __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x
   int Co = a.Co;
   int want_stats = a.stats != nullptr;
   asm volatile("" : "+v"(p_addend), "+v"(p_mask), "+v"(p_f32), "+v"(p_b16), "+v"(Co), "+v"(want_stats), "+v"(p_gate), "+v"(p_bnx));
-  {
-    const int p = lane & 31, half = lane >> 5;
-#pragma unroll
-    for (int i = 0; i < FN; ++i)
-#pragma unroll
-      for (int g = 0; g < 4; ++g)
-        *reinterpret_cast<f32x4*>(lds + p * PITCH + (i * 32 + 8 * g + 4 * half) * 4) =
-            f32x4{acc[i][4 * g], acc[i][4 * g + 1], acc[i][4 * g + 2], acc[i][4 * g + 3]};
-    if (lane < 32) {
-      const int m = m_base + lane;
-      int pix = -1;
-      if (m < Mtot) {
-        const int ow = m % a.OW, t2 = m / a.OW, oh = t2 % a.OH, n = t2 / a.OH;
-        pix = (n * a.OHf + oh * a.out_stride + a.ooh) * a.OWf + ow * a.out_stride + a.oow;
-      }
-      *reinterpret_cast<int*>(lds + 32 * PITCH + 4 * lane) = pix;
-    }
-  }
-  asm volatile("" ::: "memory");   // same wave, LDS operations stay in order: no barrier needed
   float s1[PERIOD][4], s2[PERIOD][4];
 #pragma unroll
   for (int k = 0; k < PERIOD; ++k)
 #pragma unroll
     for (int e = 0; e < 4; ++e) s1[k][e] = s2[k][e] = 0.f;
+#pragma unroll
+  for (int part = 0; part < 32 / ROWS; ++part) {
+  {
+    const int p = lane & 31, half = lane >> 5;
+    if (ROWS == 32 || p / ROWS == part) {
+#pragma unroll
+      for (int i = 0; i < FN; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<f32x4*>(lds + (p % ROWS) * PITCH + (i * 32 + 8 * g + 4 * half) * 4) =
+              f32x4{acc[i][4 * g], acc[i][4 * g + 1], acc[i][4 * g + 2], acc[i][4 * g + 3]};
+    }
+    if (lane < ROWS) {
+      const int m = m_base + part * ROWS + lane;
+      int pix = -1;
+      if (m < Mtot) {
+        const int ow = m % a.OW, t2 = m / a.OW, oh = t2 % a.OH, n = t2 / a.OH;
+        pix = (n * a.OHf + oh * a.out_stride + a.ooh) * a.OWf + ow * a.out_stride + a.oow;
+      }
+      *reinterpret_cast<int*>(lds + ROWS * PITCH + 4 * lane) = pix;
+    }
+  }
+  asm volatile("" ::: "memory");   // same wave, LDS operations stay in order: no barrier needed
   // Rows leave in groups of G iterations: first every load of the group (LDS tile, addend, mask) from addresses
   // that are safe whether or not the element exists, then the arithmetic and the stores.  Written as one
   // conditional body per iteration the loads would each sit behind a branch and pay their latency one by one.
-  constexpr int G = ITERS % 10 == 0 ? 10 : 8;
+  constexpr int G = ITERS % GROUP == 0 ? GROUP : 8;
   static_assert(ITERS % G == 0 && G % PERIOD == 0, "whole groups");
 #pragma unroll
   for (int it0 = 0; it0 < ITERS; it0 += G) {
@@ -186,7 +194,7 @@ __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x
     for (int k = 0; k < G; ++k) {
       const int q = (it0 + k) * 64 + lane;
       const int p = q / UNITS, un = q % UNITS;
-      const int pix = *reinterpret_cast<const int*>(lds + 32 * PITCH + 4 * p);
+      const int pix = *reinterpret_cast<const int*>(lds + ROWS * PITCH + 4 * p);
       const int c = c_tile + un * 4;
       ok[k] = pix >= 0 && c < Co;
       o[k] = ok[k] ? (size_t)pix * Co + c : 0;
@@ -248,7 +256,10 @@ __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x
       }
     }
   }
+  asm volatile("" ::: "memory");   // the next part overwrites the rows only after this part's reads (same wave, in order)
+  }   // part
   if (a.stats) {
+    if (PARKW != 4) __syncthreads();   // the statistics are parked where the rows were
     // Per-channel sums of the workgroup: every lane parks its partial sums in LDS, then one thread per channel
     // and value adds the lanes that carried that channel (LDS float atomics would do the same in one step but
     // run at a few lane operations per clock: 15-25 us per launch).
@@ -272,7 +283,7 @@ __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x
         const int l0 = ((un - k * 64) % UNITS + UNITS) % UNITS;   // lanes with (k*64 + lane) % UNITS == un
         for (int l = l0; l < 64; l += UNITS)
 #pragma unroll
-          for (int w = 0; w < 4; ++w) sum += park[(size_t)((w * PERIOD + k) * 64 + l) * 8 + which * 4 + e];
+          for (int w = 0; w < PARKW; ++w) sum += park[(size_t)((w * PERIOD + k) * 64 + l) * 8 + which * 4 + e];
       }
       atomicAdd(a.stats + which * a.Co + c, sum);
     }
@@ -311,6 +322,45 @@ __device__ __forceinline__ void combine_and_store32(const GatherConvArgs& a, f32
   const int wave = wave_m * 2 + wk;
   store_rows32<FN, BN>(a, keep, m_tile + wave_m * 64 + wk * 32, c_tile, lane, smem + (size_t)wave * out_stage_bytes(BN),
                        smem + (size_t)4 * out_stage_bytes(BN));
+}
+
+// End of the 256-pixel kernel: eight waves (wave_m, wk), wave_m = wave & 3 owns 64 pixels as two 32-pixel blocks j, wk =
+// wave >> 2 one half of the contraction.  The halves are added in two rounds (80 KB each: in round j the waves with
+// wk != j park block j and the waves with wk == j add it), then every wave holds the 32-pixel block j = wk of its 64
+// pixels and all eight run the output stage, 16 pixels at a time (8 regions of 10.6 KB).
+constexpr int out_stage16_bytes(int BN) { return 16 * out_stage_pitch(BN) + 128; }
+template <int FN, int BN>
+__device__ __forceinline__ void combine8_and_store32(const GatherConvArgs& a, f32x16 (&acc)[FN][2], int m_tile, int c_tile,
+                                                     int wave_m, int wk, int lane, unsigned char* smem) {
+  f32x16 keep[FN];
+#pragma unroll
+  for (int i = 0; i < FN; ++i) keep[i] = wk == 0 ? acc[i][0] : acc[i][1];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    __syncthreads();
+    f32x4* area = reinterpret_cast<f32x4*>(smem) + (size_t)(wave_m * FN) * 256;
+    if (wk != j) {
+#pragma unroll
+      for (int i = 0; i < FN; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          area[(i * 4 + q) * 64 + lane] = f32x4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+    }
+    __syncthreads();
+    if (wk == j) {
+#pragma unroll
+      for (int i = 0; i < FN; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 p = area[(i * 4 + q) * 64 + lane];
+          keep[i][4 * q] += p[0]; keep[i][4 * q + 1] += p[1]; keep[i][4 * q + 2] += p[2]; keep[i][4 * q + 3] += p[3];
+        }
+    }
+  }
+  __syncthreads();
+  const int wave = wave_m + 4 * wk;
+  store_rows32<FN, BN, 5, 16, 8>(a, keep, m_tile + wave_m * 64 + wk * 32, c_tile, lane,
+                                 smem + (size_t)wave * out_stage16_bytes(BN), smem);
 }
 
 // The wide-channel kernel (conv_wide_kernels.hip): input channels a multiple of 64.

@@ -510,6 +510,245 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
   combine_and_store32<FN, BN>(a, acc, m0, c0, wave_m, wk, lane, smem);
 }
 
+// The patch form on tiles of 256 pixels with EIGHT waves, two per SIMD, for layers whose 128-pixel tiles would need
+// two rounds of workgroups (the 320-channel layers at 16x16: 512 tiles): one round of twice as large workgroups halves
+// what every workgroup pays before and after its main loop, and a weight stage is shared by four pixel waves
+// instead of two.  Wave (wave_m = wave & 3, wk = wave >> 2) owns 64 pixels x BN channels (2 x BN/32 accumulator
+// blocks) and one 32-channel half of every 64-channel block, as in the four-wave kernel.  To fit 256 registers there
+// is a single set of fragments: the MFMAs of a half step run pixel block by pixel block (K = FN j + i), so P0 is free
+// after MFMA FN-1, W_i after MFMA FN+i, P1 after the last one, and each is read again for the next half step right
+// there; the partner wave on the SIMD covers the rest of the latency.  The second half step of a tap differs from the
+// first by bit 5 of every fragment address.  Weight stages are BN rows: with 64 rows per load instruction of the
+// workgroup BN = 160 needs 2.5 of them, so the third load of waves 4 .. 7 goes to a dump area (every wave then counts
+// the same number of loads).
+template <int BN, int PR, int WS>
+__global__ __launch_bounds__(512) void conv_patch256_kernel(GatherConvArgs a, int m_tiles, int n_tiles) {
+  constexpr int BM = 256, ROWB = 128, NWAVES = 8;
+  static_assert(BN % 32 == 0 && PR % 64 == 0, "whole DMA instructions and 32x32 blocks");
+  constexpr int JX = PR / 64, JW = (BN + 63) / 64;
+  constexpr int FM = 2, FN = BN / 32;
+  constexpr int XBYTES = PR * ROWB + 256, WBYTES = BN * ROWB;   // a patch buffer ends with two rows of zeros
+  constexpr int DUMP = 2 * XBYTES + WS * WBYTES;                // 4 KB that nobody reads
+  constexpr int LDS_BYTES = DUMP + 4096;
+  static_assert((WS - 2) * JW + JX < 64, "vmcnt range");
+  static_assert(WS >= 3 && WS <= 7, "pipeline depth");
+  static_assert((size_t)LDS_BYTES >= (size_t)4 * FN * 4096 && (size_t)LDS_BYTES >= (size_t)8 * out_stage16_bytes(BN) &&
+                (size_t)LDS_BYTES >= (size_t)2 * stats_stage_bytes(BN), "room for the output stage");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // LDS_BYTES
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave_m = wave & 3, wk = wave >> 2;
+  const int Mtot = a.N * a.OH * a.OW;
+  const int W = a.Wi, H = a.Hi;
+
+  int t = blockIdx.x;
+  const int total = m_tiles * n_tiles;
+  if ((total & 7) == 0) t = (blockIdx.x & 7) * (total >> 3) + (blockIdx.x >> 3);
+  const int m0 = (t / n_tiles) * BM, c0 = (t % n_tiles) * BN;
+
+  if (tid < 32)   // the zero rows of both patch buffers; visible after the first barrier
+    reinterpret_cast<uint4*>(smem + (tid >> 4) * XBYTES + PR * ROWB)[tid & 15] = make_uint4(0u, 0u, 0u, 0u);
+
+  // ---- per-thread DMA sources as 32-bit offsets from a wave-uniform base; rows that do not exist read some row
+  //      that does (nothing valid refers to them) ----
+  unsigned xoff[JX], woff[JW];
+#pragma unroll
+  for (int j = 0; j < JX; ++j) {
+    const int p = 8 * (NWAVES * j + wave) + (lane >> 3);
+    const int u = (lane & 7) ^ ((p >> 1) & 7);
+    int q = m0 - W - 1 + p;
+    q = q < 0 ? 0 : (q >= Mtot ? Mtot - 1 : q);
+    xoff[j] = (unsigned)q * (unsigned)(a.Ci * 2) + u * 16;
+  }
+#pragma unroll
+  for (int j = 0; j < JW; ++j) {
+    const int row = 8 * (NWAVES * j + wave) + (lane >> 3);
+    const int u = (lane & 7) ^ ((row >> 1) & 7);
+    int c = c0 + row;
+    c = c >= a.w_rows ? a.w_rows - 1 : c;
+    woff[j] = (unsigned)c * (unsigned)(a.Kw * 2) + u * 16;
+  }
+  int tko[9];
+#pragma unroll
+  for (int i = 0; i < 9; ++i) tko[i] = (a.tap[i] >> 16) * a.Ci * 2;   // byte offset of the tap's k block in a weight row
+  const int cpc = a.Ci >> 6;   // channel blocks
+
+  auto issue_x_one = [&](int j, int c) {
+    const char* base = reinterpret_cast<const char*>(a.in) + (size_t)c * 128;
+    dma16(base + (size_t)xoff[j], smem + (c & 1) * XBYTES + (8 * (NWAVES * j + wave)) * ROWB);
+  };
+  auto issue_w_one = [&](int j, int slot, int kbyte) {
+    const char* base = reinterpret_cast<const char*>(a.w) + (size_t)kbyte;
+    const int row0 = 8 * (NWAVES * j + wave);   // rows past the stage: the load still happens, into the dump area
+    unsigned char* dst = row0 < BN ? smem + 2 * XBYTES + slot * WBYTES + row0 * ROWB : smem + DUMP + (wave & 3) * 1024;
+    dma16(base + (size_t)woff[j], dst);
+  };
+#pragma unroll
+  for (int j = 0; j < JX; ++j) issue_x_one(j, 0);
+#pragma unroll
+  for (int p = 0; p < WS - 1; ++p)   // 9 taps >= WS - 1 steps always exist
+#pragma unroll
+    for (int j = 0; j < JW; ++j) issue_w_one(j, p, tko[p]);
+
+  f32x16 acc[FN][FM];
+#pragma unroll
+  for (int i = 0; i < FN; ++i)
+#pragma unroll
+    for (int j = 0; j < FM; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // ---- LDS addresses of this lane's fragments for the first 16-channel step of its half (the second one: ^ 32):
+  //      per tap and pixel block the shifted patch row in buffer 0 (or a zero row at the same bank position when the
+  //      tap falls outside the image); one address for the weights ----
+  const unsigned lds0 = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)smem);
+  unsigned xaddr[9][FM], wlane;
+#pragma unroll
+  for (int f = 0; f < FM; ++f) {
+    const int r = wave_m * 64 + f * 32 + (lane & 31);
+    const int m = m0 + r;
+    const bool inside = m < Mtot;
+    const int ow = m % a.OW, oh = (m / a.OW) % a.OH;
+#pragma unroll
+    for (int i = 0; i < 9; ++i) {
+      const int dh = (a.tap[i] & 0xff) - 8, dw = ((a.tap[i] >> 8) & 0xff) - 8;
+      const int p = r + W + 1 + dh * W + dw;
+      const bool ok = inside && (unsigned)(oh + dh) < (unsigned)H && (unsigned)(ow + dw) < (unsigned)W;
+      const int rowoff = ok ? p * ROWB : (PR + (p & 1)) * ROWB;
+      xaddr[i][f] = lds0 + rowoff + (((4 * wk + (lane >> 5)) ^ ((p >> 1) & 7)) << 4);
+    }
+  }
+  wlane = lds0 + 2 * XBYTES + (lane & 31) * ROWB + (((4 * wk + (lane >> 5)) ^ (((lane & 31) >> 1) & 7)) << 4);
+  if (lds0 & 127u) return;   // "^ 32" below flips the unit only if the LDS base is a multiple of 128 (it is 0: no static LDS)
+
+  // fragments in read order: position 0 = P0, 1 .. FN = W0 .. W(FN-1), FN+1 = P1
+  constexpr int NM = FN * FM, NFRAG = FN + FM;
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 fw[FN], fp[FM];
+  // wcur: this lane's weight address in the step's stage; SS: which 16-channel step of the half
+  auto read_pos = [&](auto pos_tag, unsigned wcur, auto tap_tag, auto ss_tag, int xshift) {
+    constexpr int POS = decltype(pos_tag)::value, T = decltype(tap_tag)::value, SS = decltype(ss_tag)::value;
+    if constexpr (POS == 0 || POS == FN + 1) {
+      constexpr int f = POS == 0 ? 0 : 1;
+      u32x4& dst = fp[f];
+      const unsigned addr = (xaddr[T][f] + xshift) ^ (SS * 32);
+      asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(addr));
+    } else {
+      constexpr int f = POS - 1;
+      u32x4& dst = fw[f];
+      const unsigned addr = wcur ^ (SS * 32);
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "i"(f * 32 * ROWB));
+    }
+  };
+  auto wait_p = [&](auto f_tag, auto n_tag) {
+    constexpr int F = decltype(f_tag)::value, N = decltype(n_tag)::value;
+    static_assert(N >= 0 && N <= 15, "lgkmcnt range");
+    u32x4& r = fp[F];
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(r) : "n"(N));
+  };
+  auto wait_w = [&](auto f_tag, auto n_tag) {
+    constexpr int F = decltype(f_tag)::value, N = decltype(n_tag)::value;
+    static_assert(N >= 0 && N <= 15, "lgkmcnt range");
+    u32x4& r = fw[F];
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(r) : "n"(N));
+  };
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+
+  wait_vmcnt<(WS - 2) * JW>();
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  static_for<NFRAG>([&](auto pos) { read_pos(pos, wlane, I0{}, I0{}, 0); });
+
+  // loads of a step's group (the weights of step i + WS - 1 and, in the first XG steps of a channel block, a share of
+  // the next block's patch) go out in the first half step after the MFMAs of slots 2, 3, 5, 7: after the barrier
+  constexpr int XG = 11 - WS;
+  constexpr int PER = (JX + XG - 1) / XG;
+  static_assert(JW + PER <= 2 + (NM - 4) / 2, "load slots of a half step");
+  auto gsize = [](int t, bool last) constexpr {
+    if (t < 0) return JW;
+    const int w = last ? (t + WS - 1 <= 8 ? JW : 0) : JW;
+    const int left = JX - t * PER;
+    const int x = (!last && t < XG && left > 0) ? (left < PER ? left : PER) : 0;
+    return w + x;
+  };
+  int slot = 0;   // weight stage of the current step
+  auto chunk_body = [&](int c, auto last_tag) {
+    constexpr bool LAST = decltype(last_tag)::value;
+    const int to_other = (c & 1) ? -XBYTES : XBYTES;   // from this block's patch buffer to the other one
+    if (c > 0) {
+#pragma unroll
+      for (int i = 0; i < 9; ++i)
+#pragma unroll
+        for (int f = 0; f < FM; ++f) xaddr[i][f] -= to_other;   // the table follows the block into its buffer
+    }
+    static_for<9>([&](auto t_tag) {
+      constexpr int T = decltype(t_tag)::value;
+      const int nslot = slot == WS - 1 ? 0 : slot + 1;
+      const int islot = slot == 0 ? WS - 1 : slot - 1;
+      const unsigned wcur = wlane + slot * WBYTES, wnext = wlane + nslot * WBYTES;
+      constexpr bool MORE = !(LAST && T == 8);            // a next step exists
+      constexpr int TT = T + WS - 1;                      // tap of the step whose weights are issued now
+      constexpr bool ISSUE_W = TT < 9 || !LAST;
+      constexpr int NWL = ISSUE_W ? JW : 0;
+      constexpr int NX = gsize(T, LAST) - NWL;            // patch loads of this group: pieces T*PER ...
+      const int kbyte = TT < 9 ? tko[TT < 9 ? TT : 0] + c * 128 : tko[TT < 9 ? 0 : TT - 9] + (c + 1) * 128;
+      using next_tap = std::integral_constant<int, (T + 1) % 9>;
+      const int next_shift = T < 8 ? 0 : to_other;
+      static_for<2>([&](auto ss_tag) {
+        constexpr int SS = decltype(ss_tag)::value;
+        constexpr bool FOLLOWS = SS == 0 || MORE;          // a half step follows this one
+        static_for<NM>([&](auto k) {
+          constexpr int K = decltype(k)::value;
+          // this half step's reads went out as P0 W0 .. W(FN-1) P1; the next one's start after MFMA FN-1
+          if constexpr (K == 0) {
+            wait_p(I0{}, std::integral_constant<int, FN + 1>{});
+            wait_w(I0{}, std::integral_constant<int, FN>{});
+          } else if constexpr (K < FN) {
+            wait_w(std::integral_constant<int, K>{}, std::integral_constant<int, FN - K>{});
+          } else if constexpr (K == FN) {
+            wait_p(I1{}, std::integral_constant<int, FOLLOWS ? 1 : 0>{});
+          }
+          acc[K % FN][K / FN] = mfma32(__builtin_bit_cast(bf16x8, fw[K % FN]), __builtin_bit_cast(bf16x8, fp[K / FN]),
+                                       acc[K % FN][K / FN]);
+          if constexpr (FOLLOWS) {
+            // the following half step: the second 16 channels of this tap, or the first of the next tap
+            auto rd = [&](auto pos_tag) {
+              if constexpr (SS == 0) read_pos(pos_tag, wcur, t_tag, I1{}, 0);
+              else read_pos(pos_tag, wnext, next_tap{}, I0{}, next_shift);
+            };
+            if constexpr (K == FN - 1) rd(I0{});
+            if constexpr (K >= FN) rd(std::integral_constant<int, K - FN + 1>{});
+            if constexpr (K == NM - 1) rd(std::integral_constant<int, FN + 1>{});
+          }
+          if constexpr (SS == 0 && MORE && K == 1) {
+            constexpr int PENDING = (WS >= 4 ? gsize(T - 1, LAST) : 0) + (WS >= 5 ? gsize(T - 2, LAST) : 0) +
+                                    (WS >= 6 ? gsize(T - 3, LAST) : 0) + (WS >= 7 ? gsize(T - 4, LAST) : 0);
+            wait_vmcnt<PENDING>();
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+          }
+          if constexpr (SS == 0 && MORE && (K == 2 || K == 3 || (K >= 5 && K % 2 == 1))) {
+            constexpr int IDX = K <= 3 ? K - 2 : 2 + (K - 5) / 2;
+            if constexpr (IDX < NWL) issue_w_one(IDX, islot, kbyte);
+            else if constexpr (IDX - NWL < NX) issue_x_one(T * PER + IDX - NWL, c + 1);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        });
+      });
+      slot = nslot;
+    });
+  };
+  for (int c = 0; c < cpc - 1; ++c) chunk_body(c, std::false_type{});
+  chunk_body(cpc - 1, std::true_type{});
+
+  wait_vmcnt<0>();
+  combine8_and_store32<FN, BN>(a, acc, m0, c0, wave_m, wk, lane, smem);
+}
+
 // the patch form needs: nine taps within +-1, unit strides, coinciding input and output grids
 static bool conv_patch_applies(const GatherConvArgs& a) {
   if (a.Ci % 64 != 0 && (a.Ci % 8 != 0 || a.Ci < 128)) return false;   // whole channel blocks, or >= 2 with a partly filled last one
@@ -550,8 +789,35 @@ static hipError_t run_patch(const GatherConvArgs& a, hipStream_t s) {
   return a.Ci % 64 == 0 ? run_patch_k<BN, PR, false>(a, s) : run_patch_k<BN, PR, true>(a, s);
 }
 
+template <int BN, int PR, int WS>
+static hipError_t run_patch256(const GatherConvArgs& a, hipStream_t s) {
+  constexpr size_t lds = (size_t)2 * (PR * 128 + 256) + (size_t)WS * BN * 128 + 4096;
+  static_assert(lds <= 160 * 1024, "LDS of one compute unit");
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_patch256_kernel<BN, PR, WS>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int Mtot = a.N * a.OH * a.OW;
+  const int m_tiles = (Mtot + 255) / 256, n_tiles = (a.Co + BN - 1) / BN;
+  static char name[64];
+  if (!name[0]) snprintf(name, sizeof(name), "conv_patch256_kernel<%d, %d, %d>", BN, PR, WS);
+  note_kernel(name);
+  hipLaunchKernelGGL((conv_patch256_kernel<BN, PR, WS>), dim3(m_tiles * n_tiles), dim3(512), lds, s, a, m_tiles, n_tiles);
+  return hipGetLastError();
+}
+
 template <int BN>
 static hipError_t run_patch_rows(const GatherConvArgs& a, hipStream_t s) {
+  // 256-pixel tiles where 128-pixel tiles need more than one round of workgroups and the larger ones still fill the chip
+  {
+    static const bool off = getenv("FDG_PATCH_128") != nullptr;   // A/B switch for measurements
+    const int Mtot = a.N * a.OH * a.OW, n_tiles = (a.Co + BN - 1) / BN;
+    const int t128 = (Mtot + 127) / 128 * n_tiles, t256 = (Mtot + 255) / 256 * n_tiles;
+    if (!off && a.Ci % 64 == 0 && t128 > 256 && t256 >= 224 && 256 + 2 * a.Wi + 2 <= 320) return run_patch256<BN, 320, 3>(a, s);
+  }
   const int rows = 128 + 2 * a.Wi + 2;   // patch rows in use
   if (rows <= 160) return run_patch<BN, 160>(a, s);
   if (rows <= 192) return run_patch<BN, 192>(a, s);
