@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..5 (default 4: WRN-28-10 top module)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--replay", action="store_true",
+                    help="FDG_SAVE_INPUT_AND_REPLAY: a saved forward is its input and weight snapshot; the backward runs the forward again")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run 3 plain device copies of 1 GiB (float32): the known traffic a profiler's HBM counters "
                          "are scaled by")
@@ -134,7 +136,7 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    mod = FdgModule(spec, dev)
+    mod = FdgModule(spec, dev, save_mode=1 if args.replay else 0)
     mod.set_params(W.make_params(spec))
 
     # a small pool of resident inputs, cycled, so consecutive steps do not re-read the same lines
@@ -220,6 +222,8 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": spec.name, "batch": spec.n, "delay": spec.delay, "beta": spec.beta,
+                   "saved_forward": "input + weight snapshot, replayed by the backward" if args.replay else "activations",
+                   "workspace_MiB": mod.workspace_bytes / 2 ** 20,
                    "params": W.param_count(spec), "useful_conv_gflop_per_step": W.conv_flops(spec) / 1e9},
         "step_tflops": W.conv_flops(spec) / (ms_per_step * 1e-3) / 1e12,
         "roofline": roofline,

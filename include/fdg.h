@@ -98,6 +98,22 @@ size_t fdg_module_workspace_bytes(const fdg_module_desc* desc);
 fdg_status fdg_module_create(const fdg_module_desc* desc, void* dev_workspace, size_t bytes,
                              void* hip_stream, fdg_module** out);
 
+/* What a saved forward (the "saved computation graph" of Fig. 1(b)) consists of.
+ *   FDG_SAVE_ACTIVATIONS      : every intermediate the backward reads, written once by the forward.  The ring costs
+ *                               delay+1 sets of activations.
+ *   FDG_SAVE_INPUT_AND_REPLAY : the module input (fp32, as given) and the weight snapshot only.  The delayed backward
+ *                               first runs the forward again on that input with that snapshot (the recomputation of
+ *                               feature replay, Section II, here with FDG's own stale weights, so Eq. 10 is unchanged)
+ *                               into ONE set of activations shared by all contexts.  Results are those of
+ *                               FDG_SAVE_ACTIVATIONS up to the order of floating-point sums; the running statistics of
+ *                               batch normalisation move only in fdg_forward.  Costs one more forward per backward.
+ * fdg_module_workspace_bytes / fdg_module_create are the _ex forms with FDG_SAVE_ACTIVATIONS; everything said
+ * there holds here.  Any other save_mode: 0 bytes / FDG_ERR_INVALID_ARG.                                          */
+typedef enum { FDG_SAVE_ACTIVATIONS = 0, FDG_SAVE_INPUT_AND_REPLAY = 1 } fdg_save_mode;
+size_t fdg_module_workspace_bytes_ex(const fdg_module_desc* desc, int32_t save_mode);
+fdg_status fdg_module_create_ex(const fdg_module_desc* desc, int32_t save_mode, void* dev_workspace, size_t bytes,
+                                void* hip_stream, fdg_module** out);
+
 /* Forward step of Section III-A: run the layers on x with the CURRENT weights and push a context
  * (saved activations, batch statistics, and a snapshot of the weights used) into the ring.
  *   x_dev      : [n, c_in, h_in, w_in] fp32 NCHW, read only.

@@ -296,8 +296,14 @@ class OracleModule:
     descriptor (n, c_in, h_in, w_in, layers[kind,c_in,c_out,stride], delay, is_bottom, num_classes,
     beta, momentum, weight_decay, bn_eps, bn_momentum)."""
 
-    def __init__(self, spec, dtype=np.float32, storage: str = "fp32"):
-        assert storage in ("fp32", "bf16")
+    def __init__(self, spec, dtype=np.float32, storage: str = "fp32", save: str = "activations"):
+        """save = "activations": a saved forward keeps every intermediate (the saved graph of Fig. 1(b)).
+        save = "input": it keeps the module input, the labels and the parameters of that forward only, and
+        the delayed backward first runs the same forward again (recomputation as in feature replay,
+        Section II, but at the STALE parameters, so that Eq. 10 is evaluated as before); running
+        statistics move only in forward()."""
+        assert storage in ("fp32", "bf16") and save in ("activations", "input")
+        self.save = save
         self.spec = spec
         self.dt = np.dtype(dtype)
         self.k = Kernels(dtype)
@@ -316,6 +322,7 @@ class OracleModule:
         self.seq_fwd = 0   # number of forwards done  = sequence number of the next forward
         self.seq_bwd = 0   # number of backwards done = sequence number of the next context to pop
         self.is_top = bool(spec.layers) and spec.layers[-1].kind in (HEAD_POSTACT, HEAD_PREACT)
+        self._move_running = True
 
     # ---- accessors ---------------------------------------------------------------------------
     def param_count(self) -> int:
@@ -346,12 +353,13 @@ class OracleModule:
     # ---- batch normalisation with running statistics -----------------------------------------
     def _bn(self, key: str, x, th: _Flat, tape: dict):
         y, mean, var, invstd = self.k.bn_fwd(x, th[key + ".gamma"], th[key + ".beta"], self.spec.bn_eps)
-        M = x.shape[0] * x.shape[2] * x.shape[3]
-        mom = self.spec.bn_momentum
-        rm, rv = self.running[key]
-        unbiased = var * (M / (M - 1.0)) if M > 1 else var
-        self.running[key] = [((1.0 - mom) * rm + mom * mean).astype(self.dt),
-                             ((1.0 - mom) * rv + mom * unbiased).astype(self.dt)]
+        if self._move_running:
+            M = x.shape[0] * x.shape[2] * x.shape[3]
+            mom = self.spec.bn_momentum
+            rm, rv = self.running[key]
+            unbiased = var * (M / (M - 1.0)) if M > 1 else var
+            self.running[key] = [((1.0 - mom) * rm + mom * mean).astype(self.dt),
+                                 ((1.0 - mom) * rv + mom * unbiased).astype(self.dt)]
         tape[key] = (x, mean, invstd)
         return y
 
@@ -383,8 +391,20 @@ class OracleModule:
         z is the residual stream in full precision, zb its stored copy (conv / BN operand)."""
         if len(self.fifo) >= self.spec.delay + 1:
             raise QueueFull()
-        k, q = self.k, self._q
         th = self._stored_weights(self.theta.copy())   # parameters of THIS iteration, kept for the backward
+        x = np.array(x, dtype=self.dt, order="C")
+        out, tapes = self._layers(x, labels, th, move_running=True)
+        if self.save == "input":
+            self.fifo.append({"theta": th, "x": x, "labels": None if labels is None else np.array(labels), "seq": self.seq_fwd})
+        else:
+            self.fifo.append({"theta": th, "tapes": tapes, "seq": self.seq_fwd})
+        self.seq_fwd += 1
+        return out
+
+    def _layers(self, x, labels, th: _Flat, move_running: bool):
+        """The module's layers on x with parameters th: (output, what every layer keeps for its backward)."""
+        self._move_running = move_running
+        k, q = self.k, self._q
         tapes: List[dict] = []
         z = np.ascontiguousarray(x, dtype=self.dt)
         assert z.shape == (self.spec.n, self.spec.c_in, self.spec.h_in, self.spec.w_in)
@@ -434,9 +454,7 @@ class OracleModule:
             tapes.append(t)
         if out is None:
             out = z
-        self.fifo.append({"theta": th, "tapes": tapes, "seq": self.seq_fwd})
-        self.seq_fwd += 1
-        return out
+        return out, tapes
 
     # ---- delayed backward ----------------------------------------------------------------------
     def backward_delayed(self, grad_out=None):
@@ -448,7 +466,11 @@ class OracleModule:
         ctx = self.fifo.popleft()
         assert ctx["seq"] == self.seq_bwd
         self.seq_bwd += 1
-        k, q, th, tapes = self.k, self._q, ctx["theta"], ctx["tapes"]
+        k, q, th = self.k, self._q, ctx["theta"]
+        if self.save == "input":    # the saved forward again, on its input with its parameters
+            _, tapes = self._layers(ctx["x"], ctx["labels"], th, move_running=False)
+        else:
+            tapes = ctx["tapes"]
         g = _Flat(self.layout, self.dt)
         if self.is_top:
             assert grad_out is None

@@ -43,7 +43,7 @@ class fdg_module_desc(ctypes.Structure):
 
 _lib: Optional[ctypes.CDLL] = None
 
-EXPORTS = ["fdg_module_workspace_bytes", "fdg_module_create", "fdg_forward", "fdg_backward_delayed", "fdg_update",
+EXPORTS = ["fdg_module_workspace_bytes", "fdg_module_create", "fdg_module_workspace_bytes_ex", "fdg_module_create_ex", "fdg_forward", "fdg_backward_delayed", "fdg_update",
            "fdg_destroy", "fdg_param_count", "fdg_set_params", "fdg_get_params", "fdg_get_grads", "fdg_get_momentum",
            "fdg_bn_stat_count", "fdg_get_bn_running", "fdg_output_shape", "fdg_queue_state", "fdg_status_string",
            "fdg_profile_enable", "fdg_profile_read", "fdg_input_shape", "fdg_module_traits",
@@ -63,6 +63,8 @@ def load() -> ctypes.CDLL:
     dp = ctypes.POINTER(fdg_module_desc)
     lib.fdg_module_workspace_bytes.argtypes, lib.fdg_module_workspace_bytes.restype = [dp], sz
     lib.fdg_module_create.argtypes, lib.fdg_module_create.restype = [dp, vp, sz, vp, ctypes.POINTER(vp)], i32
+    lib.fdg_module_workspace_bytes_ex.argtypes, lib.fdg_module_workspace_bytes_ex.restype = [dp, i32], sz
+    lib.fdg_module_create_ex.argtypes, lib.fdg_module_create_ex.restype = [dp, i32, vp, sz, vp, ctypes.POINTER(vp)], i32
     lib.fdg_forward.argtypes, lib.fdg_forward.restype = [vp, vp, vp, vp, vp], i32
     lib.fdg_backward_delayed.argtypes, lib.fdg_backward_delayed.restype = [vp, vp, vp, vp], i32
     lib.fdg_update.argtypes, lib.fdg_update.restype = [vp, f32, vp], i32
@@ -134,6 +136,24 @@ def fdg_module_create(spec, workspace, stream=None) -> int:
     return out.value
 
 
+FDG_SAVE_ACTIVATIONS, FDG_SAVE_INPUT_AND_REPLAY = 0, 1
+
+
+def fdg_module_workspace_bytes_ex(spec, save_mode: int) -> int:
+    d, keep = make_desc(spec)
+    return int(load().fdg_module_workspace_bytes_ex(ctypes.byref(d), int(save_mode)))
+
+
+def fdg_module_create_ex(spec, save_mode: int, workspace, stream=None) -> int:
+    d, keep = make_desc(spec)
+    out = ctypes.c_void_p()
+    st = load().fdg_module_create_ex(ctypes.byref(d), int(save_mode), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream_handle(stream), ctypes.byref(out))
+    if st != FDG_OK:
+        raise FdgError(st, "fdg_module_create_ex")
+    return out.value
+
+
 def fdg_forward(handle: int, x, labels, y, stream=None) -> int:
     return int(load().fdg_forward(handle, _ptr(x), _ptr(labels), _ptr(y), _stream_handle(stream)))
 
@@ -154,19 +174,20 @@ def fdg_destroy(handle: Optional[int]) -> None:
 class FdgModule:
     """Owns the workspace tensor and the handle of one module; every method is one C call."""
 
-    def __init__(self, spec, device="cuda:0", stream=None):
+    def __init__(self, spec, device="cuda:0", stream=None, save_mode=FDG_SAVE_ACTIVATIONS):
         import torch
         self.torch = torch
         self.spec = spec
         self.device = torch.device(device)
-        nbytes = fdg_module_workspace_bytes(spec)
+        self.save_mode = int(save_mode)
+        nbytes = fdg_module_workspace_bytes_ex(spec, self.save_mode)
         if nbytes == 0:
             raise FdgError(FDG_ERR_UNSUPPORTED, "fdg_module_workspace_bytes")
         self.workspace_bytes = nbytes
         self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
         off = (-self.workspace.data_ptr()) % 256
         self._ws_view = self.workspace[off:off + nbytes]
-        self.handle = fdg_module_create(spec, self._ws_view, stream)
+        self.handle = fdg_module_create_ex(spec, self.save_mode, self._ws_view, stream)
         shp = (ctypes.c_int32 * 4)()
         load().fdg_output_shape(self.handle, ctypes.byref(shp))
         self.out_shape = tuple(int(v) for v in shp)

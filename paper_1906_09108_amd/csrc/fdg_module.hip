@@ -53,6 +53,7 @@ struct Plan {
   std::vector<BnInfo> bns;
   std::vector<ParamTensor> ptensors;
   bool is_top = false;
+  bool replay = false;         // a saved forward is its input and weight snapshot; the backward runs the forward again
   int Cp_in = 0;               // channel pitch of the module input copy
   int out_c = 0, out_h = 0, out_w = 0;
   size_t ext_params = 0;       // external parameter count
@@ -66,14 +67,20 @@ struct Plan {
   int head_C = 0, head_HW = 0;
   // workspace byte offsets
   size_t o_params = 0, o_mom = 0, o_grads = 0, o_bsums = 0, o_running = 0, o_table = 0, o_slots = 0, slot_bytes = 0;
-  size_t s_warena = 0, s_small = 0, s_sums = 0, s_xin = 0, s_acts = 0, s_pooled = 0, s_dl = 0, s_logits = 0, s_labels = 0;
+  // per saved forward: weight snapshot, small-parameter snapshot, labels, (replay) the fp32 NCHW input
+  size_t s_warena = 0, s_small = 0, s_labels = 0, s_xcopy = 0;
+  // intermediates: inside every slot, or (replay) once per module at o_inter
+  size_t s_sums = 0, s_xin = 0, s_acts = 0, s_pooled = 0, s_dl = 0, s_logits = 0;
+  size_t o_inter = 0, inter_bytes = 0;
   size_t o_S[2] = {0, 0}, o_G[2] = {0, 0}, o_GB[2] = {0, 0}, o_T[2] = {0, 0}, o_TP = 0, o_dp = 0;
   size_t o_wscratch = 0, wscratch_bytes = 0;   // partial sums of the split weight gradient
   size_t total = 0;
 };
 
-bool build_plan(const fdg_module_desc* desc, Plan& p, fdg_status* why) {
+bool build_plan(const fdg_module_desc* desc, int save_mode, Plan& p, fdg_status* why) {
   *why = FDG_ERR_INVALID_ARG;
+  if (save_mode != FDG_SAVE_ACTIVATIONS && save_mode != FDG_SAVE_INPUT_AND_REPLAY) return false;
+  p.replay = save_mode == FDG_SAVE_INPUT_AND_REPLAY;
   if (!desc || !desc->layers || desc->num_layers <= 0) return false;
   if (desc->n <= 0 || desc->c_in <= 0 || desc->h_in <= 0 || desc->w_in <= 0 || desc->delay < 0) return false;
   if (!(desc->beta > 0.f && desc->beta <= 1.f) || !(desc->bn_eps > 0.f)) return false;
@@ -241,28 +248,35 @@ bool build_plan(const fdg_module_desc* desc, Plan& p, fdg_status* why) {
   p.o_bsums = take(p.stat_floats * 4);
   p.o_running = take(p.stat_floats * 4);
   p.o_table = take(p.convs.size() * sizeof(WeightEmitEntry));
-  {  // one slot
-    size_t so = 0;
+  {  // one slot; the intermediates follow the snapshots inside it, or form a region of their own (replay)
+    size_t so = 0, io = 0;
     auto stake = [&](size_t bytes) { const size_t at = so; so += align_up(bytes, kAlign); return at; };
+    auto itake = [&](size_t bytes) {
+      size_t& o2 = p.replay ? io : so;
+      const size_t at = o2; o2 += align_up(bytes, kAlign); return at;
+    };
     p.s_warena = stake(p.warena_elems * 2);
     p.s_small = stake(p.small_count * 4);
-    p.s_sums = stake(p.stat_floats * 4);
-    p.s_xin = stake((size_t)N * desc->h_in * desc->w_in * p.Cp_in * 2);
-    p.s_acts = stake(act_bytes);
+    if (p.is_top) p.s_labels = stake((size_t)N * 4);
+    if (p.replay) p.s_xcopy = stake((size_t)N * desc->c_in * desc->h_in * desc->w_in * 4);
+    p.s_sums = itake(p.stat_floats * 4);
+    p.s_xin = itake((size_t)N * desc->h_in * desc->w_in * p.Cp_in * 2);
+    p.s_acts = itake(act_bytes);
     if (p.is_top) {
-      p.s_pooled = stake((size_t)N * p.head_C * 4);
-      p.s_dl = stake((size_t)N * desc->num_classes * 4);
-      p.s_logits = stake((size_t)N * desc->num_classes * 4);
-      p.s_labels = stake((size_t)N * 4);
+      p.s_pooled = itake((size_t)N * p.head_C * 4);
+      p.s_dl = itake((size_t)N * desc->num_classes * 4);
+      p.s_logits = itake((size_t)N * desc->num_classes * 4);
     }
     p.slot_bytes = so;
+    p.inter_bytes = io;
   }
   p.o_slots = take(p.slot_bytes * (size_t)(desc->delay + 1));
+  p.o_inter = take(p.inter_bytes);
   for (int i = 0; i < 2; ++i) p.o_S[i] = take(p.maxE * 4);
   for (int i = 0; i < 2; ++i) p.o_G[i] = take(p.maxE * 4);
   for (int i = 0; i < 2; ++i) p.o_GB[i] = take(p.maxE * 2);
   for (int i = 0; i < 2; ++i) p.o_T[i] = take(p.maxE * 2);
-  p.o_TP = take(p.maxE * 4);
+  p.o_TP = take(std::max(p.maxE, p.is_top ? (size_t)1 + (size_t)N * desc->num_classes : (size_t)0) * 4);
   p.o_dp = take(p.is_top ? (size_t)N * p.head_C * 4 : 0);
   for (const ConvInfo& ci : p.convs) p.wscratch_bytes = std::max(p.wscratch_bytes, conv_wgrad_scratch_bytes(ci.sh));
   p.o_wscratch = take(p.wscratch_bytes);
@@ -353,24 +367,30 @@ namespace {
     }                                      \
   } while (0)
 
-// views into one slot
+// views into one saved forward: `base` its slot, `inter` where its intermediates live
 struct SlotView {
   const fdg_module* m;
   char* base;
+  char* inter;
   bf16_t* warena() const { return reinterpret_cast<bf16_t*>(base + m->p.s_warena); }
   bf16_t* W(const ConvInfo& c) const { return warena() + c.w_off; }
   bf16_t* Wt(const ConvInfo& c) const { return warena() + c.wt_off; }
   float* small() const { return reinterpret_cast<float*>(base + m->p.s_small); }
   // snapshot of a small parameter given its offset in the parameter arena
   float* snap(size_t arena_off) const { return small() + (arena_off - m->p.small_off); }
-  float* sums(const BnInfo& b) const { return reinterpret_cast<float*>(base + m->p.s_sums) + b.stat_off; }
-  bf16_t* xin() const { return reinterpret_cast<bf16_t*>(base + m->p.s_xin); }
-  bf16_t* act(size_t off) const { return reinterpret_cast<bf16_t*>(base + m->p.s_acts + off); }
-  float* pooled() const { return reinterpret_cast<float*>(base + m->p.s_pooled); }
-  float* dl() const { return reinterpret_cast<float*>(base + m->p.s_dl); }
-  float* logits() const { return reinterpret_cast<float*>(base + m->p.s_logits); }
+  float* sums(const BnInfo& b) const { return reinterpret_cast<float*>(inter + m->p.s_sums) + b.stat_off; }
+  bf16_t* xin() const { return reinterpret_cast<bf16_t*>(inter + m->p.s_xin); }
+  bf16_t* act(size_t off) const { return reinterpret_cast<bf16_t*>(inter + m->p.s_acts + off); }
+  float* pooled() const { return reinterpret_cast<float*>(inter + m->p.s_pooled); }
+  float* dl() const { return reinterpret_cast<float*>(inter + m->p.s_dl); }
+  float* logits() const { return reinterpret_cast<float*>(inter + m->p.s_logits); }
   int32_t* labels() const { return reinterpret_cast<int32_t*>(base + m->p.s_labels); }
+  float* xcopy() const { return reinterpret_cast<float*>(base + m->p.s_xcopy); }
 };
+inline SlotView view_of(const fdg_module* m, int64_t seq) {
+  char* base = m->slot(seq);
+  return SlotView{m, base, m->p.replay ? m->ws + m->p.o_inter : base};
+}
 
 // Brackets the launches made in its lifetime with two events when profiling is on.
 struct ProfScope {
@@ -492,18 +512,19 @@ hipError_t bn_stats(const SlotView& v, const BnInfo& b, const bf16_t* x, hipStre
   return launch_bn_stats(x, v.sums(b), b.M, b.C, s);
 }
 
-// forward apply with the CURRENT parameters; also moves the running statistics
+// forward apply with the parameters of the slot's snapshot (taken from the current ones just before the forward);
+// moves the running statistics unless this is the replay of a saved forward
 hipError_t bn_apply(const fdg_module* m, const SlotView& v, const BnInfo& b, const bf16_t* x, const float* res,
-                    const BnInfo* b2, const bf16_t* x2, float* out_f32, bf16_t* out_b16, hipStream_t s) {
+                    const BnInfo* b2, const bf16_t* x2, float* out_f32, bf16_t* out_b16, bool replayed, hipStream_t s) {
   BnApplyArgs a{};
-  a.x = x; a.sums = v.sums(b); a.gamma = m->params() + b.gamma_off; a.beta = m->params() + b.beta_off;
+  a.x = x; a.sums = v.sums(b); a.gamma = v.snap(b.gamma_off); a.beta = v.snap(b.beta_off);
   a.res_f32 = res;
   if (b2) {
-    a.x2 = x2; a.sums2 = v.sums(*b2); a.gamma2 = m->params() + b2->gamma_off; a.beta2 = m->params() + b2->beta_off;
-    a.run_mean2 = m->running() + b2->stat_off; a.run_var2 = m->running() + b2->stat_off + b2->C;
+    a.x2 = x2; a.sums2 = v.sums(*b2); a.gamma2 = v.snap(b2->gamma_off); a.beta2 = v.snap(b2->beta_off);
+    if (!replayed) { a.run_mean2 = m->running() + b2->stat_off; a.run_var2 = m->running() + b2->stat_off + b2->C; }
   }
   a.out_f32 = out_f32; a.out_b16 = out_b16;
-  a.run_mean = m->running() + b.stat_off; a.run_var = m->running() + b.stat_off + b.C;
+  if (!replayed) { a.run_mean = m->running() + b.stat_off; a.run_var = m->running() + b.stat_off + b.C; }
   a.M = b.M; a.C = b.C; a.eps = m->p.d.bn_eps; a.momentum = m->p.d.bn_momentum; a.relu = 1;
   ProfScope ps(m, PC_BN_APPLY, 0, (double)b.M * b.C * (2 + (res ? 4 : 0) + (b2 ? 2 : 0) + (out_f32 ? 4 : 0) + (out_b16 ? 2 : 0)), s);
   return launch_bn_apply(a, s);
@@ -572,6 +593,86 @@ hipError_t dgrad_relu_bn_backward(const fdg_module* m, const SlotView& v, const 
   return bn_backward(m, v, b, g, false, gate, x, bn_addend, out_f32, out_b16, s);
 }
 
+// The layers of the module on x (fp32 NCHW) with the weights of slot v, every intermediate the backward needs
+// written where v keeps them.  `replayed`: this forward ran before (v's snapshot and labels are in place); running
+// statistics stay as they are and y_dev may be NULL (a head then needs it as scratch for loss and logits).
+fdg_status forward_pass(fdg_module* m, const SlotView& v, const float* x_dev, float* y_dev, bool replayed, hipStream_t s) {
+  const Plan& p = m->p;
+  const int N = p.d.n;
+  if (p.stat_floats) FDG_TRY(launch_fill_zero(v.sums(p.bns[0]), align_up(p.stat_floats * 4, 16), s));
+  // module input: fp32 NCHW -> fp32 NHWC stream + bf16 NHWC copy (kept for the backward)
+  int cur = 0;
+  FDG_TRY(launch_nchw_to_nhwc(x_dev, (p.d.c_in % 8 == 0) ? m->S(cur) : nullptr, v.xin(), N, p.d.c_in, p.d.h_in * p.d.w_in,
+                              p.Cp_in, 1.f, s));
+  const bf16_t* cur_b = v.xin();
+  bool stats_ready = false;   // the sums of this layer's leading BN were taken by the producer of its input
+  for (size_t li = 0; li < p.L.size(); ++li) {
+    const LayerPlan& L = p.L[li];
+    const int nxt = cur ^ 1;
+    bool next_ready = false;
+    if (L.kind == FDG_STEM_CONV_BN_RELU) {
+      const ConvInfo& c0 = p.convs[L.conv[0]];
+      const BnInfo& b0 = p.bns[L.bn[0]];
+      FDG_TRY(mconv_forward(m, c0, cur_b, v.W(c0), nullptr, nullptr, v.act(L.act[0]), v.sums(b0), s));
+      FDG_TRY(bn_apply(m, v, b0, v.act(L.act[0]), nullptr, nullptr, nullptr, m->S(nxt), v.act(L.out_b), replayed, s));
+    } else if (L.kind == FDG_BASIC_POSTACT) {
+      const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]];
+      const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]];
+      bf16_t *t_c1 = v.act(L.act[0]), *t_a1 = v.act(L.act[1]), *t_c2 = v.act(L.act[2]);
+      FDG_TRY(mconv_forward(m, c1, cur_b, v.W(c1), nullptr, nullptr, t_c1, v.sums(b1), s));
+      FDG_TRY(bn_apply(m, v, b1, t_c1, nullptr, nullptr, nullptr, nullptr, t_a1, replayed, s));
+      FDG_TRY(mconv_forward(m, c2, t_a1, v.W(c2), nullptr, nullptr, t_c2, v.sums(b2), s));
+      if (L.projects) {
+        const ConvInfo& cp = p.convs[L.conv[2]];
+        const BnInfo& bp = p.bns[L.bn[2]];
+        bf16_t* t_p = v.act(L.act[3]);
+        FDG_TRY(mconv_forward(m, cp, cur_b, v.W(cp), nullptr, nullptr, t_p, v.sums(bp), s));
+        FDG_TRY(bn_apply(m, v, b2, t_c2, nullptr, &bp, t_p, m->S(nxt), v.act(L.out_b), replayed, s));
+      } else {
+        FDG_TRY(bn_apply(m, v, b2, t_c2, m->S(cur), nullptr, nullptr, m->S(nxt), v.act(L.out_b), replayed, s));
+      }
+    } else if (L.kind == FDG_BASIC_PREACT) {
+      const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]];
+      const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]];
+      bf16_t *t_o1 = v.act(L.act[0]), *t_c1 = v.act(L.act[1]), *t_o2 = v.act(L.act[2]);
+      if (!stats_ready) FDG_TRY(bn_stats(v, b1, cur_b, s));
+      FDG_TRY(bn_apply(m, v, b1, cur_b, nullptr, nullptr, nullptr, nullptr, t_o1, replayed, s));
+      FDG_TRY(mconv_forward(m, c1, t_o1, v.W(c1), nullptr, nullptr, t_c1, v.sums(b2), s));
+      FDG_TRY(bn_apply(m, v, b2, t_c1, nullptr, nullptr, nullptr, nullptr, t_o2, replayed, s));
+      const float* shortcut = m->S(cur);
+      if (L.projects) {
+        const ConvInfo& cp = p.convs[L.conv[2]];
+        FDG_TRY(mconv_forward(m, cp, t_o1, v.W(cp), nullptr, m->TP(), nullptr, nullptr, s));
+        shortcut = m->TP();
+      }
+      // the block output is the next layer's BN input when that layer is pre-activated: take its sums here
+      float* next_stats = nullptr;
+      if (li + 1 < p.L.size() && (p.L[li + 1].kind == FDG_BASIC_PREACT || p.L[li + 1].kind == FDG_HEAD_PREACT))
+        next_stats = v.sums(p.bns[p.L[li + 1].bn[0]]);
+      FDG_TRY(mconv_forward(m, c2, t_o2, v.W(c2), shortcut, m->S(nxt), v.act(L.out_b), next_stats, s));
+      next_ready = next_stats != nullptr;
+    } else {  // heads
+      const bf16_t* o = cur_b;
+      if (L.kind == FDG_HEAD_PREACT) {
+        const BnInfo& b0 = p.bns[L.bn[0]];
+        if (!stats_ready) FDG_TRY(bn_stats(v, b0, cur_b, s));
+        FDG_TRY(bn_apply(m, v, b0, cur_b, nullptr, nullptr, nullptr, nullptr, v.act(L.act[0]), replayed, s));
+        o = v.act(L.act[0]);
+      }
+      const int J = p.d.num_classes;
+      FDG_TRY(launch_avgpool(o, v.pooled(), N, p.head_HW, p.head_C, s));
+      FDG_TRY(launch_fc_fwd(v.pooled(), v.snap(L.fc_w_off), v.snap(L.fc_b_off), v.logits(), N, p.head_C, J, s));
+      FDG_TRY(launch_softmax_ce(v.logits(), v.labels(), y_dev, v.dl(), N, J, s));
+      break;
+    }
+    cur = nxt;
+    cur_b = v.act(L.out_b);
+    stats_ready = next_ready;
+  }
+  if (!p.is_top && y_dev) FDG_TRY(launch_nhwc_to_nchw(m->S(cur), y_dev, N, p.out_c, p.out_h * p.out_w, p.out_c, s));
+  return FDG_OK;
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------------------------------------
@@ -579,21 +680,27 @@ hipError_t dgrad_relu_bn_backward(const fdg_module* m, const SlotView& v, const 
 // ------------------------------------------------------------------------------------------------
 extern "C" {
 
-size_t fdg_module_workspace_bytes(const fdg_module_desc* desc) {
+size_t fdg_module_workspace_bytes_ex(const fdg_module_desc* desc, int32_t save_mode) {
   Plan p;
   fdg_status why;
-  if (!build_plan(desc, p, &why)) return 0;
+  if (!build_plan(desc, save_mode, p, &why)) return 0;
   return p.total;
 }
+size_t fdg_module_workspace_bytes(const fdg_module_desc* desc) { return fdg_module_workspace_bytes_ex(desc, FDG_SAVE_ACTIVATIONS); }
 
 fdg_status fdg_module_create(const fdg_module_desc* desc, void* dev_workspace, size_t bytes, void* hip_stream,
                              fdg_module** out) {
+  return fdg_module_create_ex(desc, FDG_SAVE_ACTIVATIONS, dev_workspace, bytes, hip_stream, out);
+}
+
+fdg_status fdg_module_create_ex(const fdg_module_desc* desc, int32_t save_mode, void* dev_workspace, size_t bytes,
+                                void* hip_stream, fdg_module** out) {
   if (!out) return FDG_ERR_INVALID_ARG;
   *out = nullptr;
   fdg_module* m = new (std::nothrow) fdg_module();
   if (!m) return FDG_ERR_INVALID_ARG;
   fdg_status why;
-  if (!build_plan(desc, m->p, &why)) {
+  if (!build_plan(desc, save_mode, m->p, &why)) {
     delete m;
     return why;
   }
@@ -643,7 +750,7 @@ fdg_status fdg_forward(fdg_module* m, const float* x_dev, const int32_t* labels_
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   m->last_stream = s;
   FDG_TRY(side_join(m, s));
-  SlotView v{m, m->slot(m->seq_fwd)};
+  SlotView v = view_of(m, m->seq_fwd);
   const int N = p.d.n;
   // snapshot of the weights this forward uses (Eq. 10 evaluates the backward at these)
   {
@@ -653,78 +760,9 @@ fdg_status fdg_forward(fdg_module* m, const float* x_dev, const int32_t* labels_
   }
   if (p.small_count)
     FDG_TRY(hipMemcpyAsync(v.small(), m->params() + p.small_off, p.small_count * 4, hipMemcpyDeviceToDevice, s));
-  if (p.stat_floats) FDG_TRY(launch_fill_zero(v.sums(p.bns[0]), align_up(p.stat_floats * 4, 16), s));
   if (p.is_top) FDG_TRY(hipMemcpyAsync(v.labels(), labels_dev, (size_t)N * 4, hipMemcpyDeviceToDevice, s));
-  // module input: fp32 NCHW -> fp32 NHWC stream + bf16 NHWC copy (kept for the backward)
-  int cur = 0;
-  FDG_TRY(launch_nchw_to_nhwc(x_dev, (p.d.c_in % 8 == 0) ? m->S(cur) : nullptr, v.xin(), N, p.d.c_in, p.d.h_in * p.d.w_in,
-                              p.Cp_in, 1.f, s));
-  const bf16_t* cur_b = v.xin();
-  bool stats_ready = false;   // the sums of this layer's leading BN were taken by the producer of its input
-  for (size_t li = 0; li < p.L.size(); ++li) {
-    const LayerPlan& L = p.L[li];
-    const int nxt = cur ^ 1;
-    bool next_ready = false;
-    if (L.kind == FDG_STEM_CONV_BN_RELU) {
-      const ConvInfo& c0 = p.convs[L.conv[0]];
-      const BnInfo& b0 = p.bns[L.bn[0]];
-      FDG_TRY(mconv_forward(m, c0, cur_b, v.W(c0), nullptr, nullptr, v.act(L.act[0]), v.sums(b0), s));
-      FDG_TRY(bn_apply(m, v, b0, v.act(L.act[0]), nullptr, nullptr, nullptr, m->S(nxt), v.act(L.out_b), s));
-    } else if (L.kind == FDG_BASIC_POSTACT) {
-      const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]];
-      const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]];
-      bf16_t *t_c1 = v.act(L.act[0]), *t_a1 = v.act(L.act[1]), *t_c2 = v.act(L.act[2]);
-      FDG_TRY(mconv_forward(m, c1, cur_b, v.W(c1), nullptr, nullptr, t_c1, v.sums(b1), s));
-      FDG_TRY(bn_apply(m, v, b1, t_c1, nullptr, nullptr, nullptr, nullptr, t_a1, s));
-      FDG_TRY(mconv_forward(m, c2, t_a1, v.W(c2), nullptr, nullptr, t_c2, v.sums(b2), s));
-      if (L.projects) {
-        const ConvInfo& cp = p.convs[L.conv[2]];
-        const BnInfo& bp = p.bns[L.bn[2]];
-        bf16_t* t_p = v.act(L.act[3]);
-        FDG_TRY(mconv_forward(m, cp, cur_b, v.W(cp), nullptr, nullptr, t_p, v.sums(bp), s));
-        FDG_TRY(bn_apply(m, v, b2, t_c2, nullptr, &bp, t_p, m->S(nxt), v.act(L.out_b), s));
-      } else {
-        FDG_TRY(bn_apply(m, v, b2, t_c2, m->S(cur), nullptr, nullptr, m->S(nxt), v.act(L.out_b), s));
-      }
-    } else if (L.kind == FDG_BASIC_PREACT) {
-      const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]];
-      const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]];
-      bf16_t *t_o1 = v.act(L.act[0]), *t_c1 = v.act(L.act[1]), *t_o2 = v.act(L.act[2]);
-      if (!stats_ready) FDG_TRY(bn_stats(v, b1, cur_b, s));
-      FDG_TRY(bn_apply(m, v, b1, cur_b, nullptr, nullptr, nullptr, nullptr, t_o1, s));
-      FDG_TRY(mconv_forward(m, c1, t_o1, v.W(c1), nullptr, nullptr, t_c1, v.sums(b2), s));
-      FDG_TRY(bn_apply(m, v, b2, t_c1, nullptr, nullptr, nullptr, nullptr, t_o2, s));
-      const float* shortcut = m->S(cur);
-      if (L.projects) {
-        const ConvInfo& cp = p.convs[L.conv[2]];
-        FDG_TRY(mconv_forward(m, cp, t_o1, v.W(cp), nullptr, m->TP(), nullptr, nullptr, s));
-        shortcut = m->TP();
-      }
-      // the block output is the next layer's BN input when that layer is pre-activated: take its sums here
-      float* next_stats = nullptr;
-      if (li + 1 < p.L.size() && (p.L[li + 1].kind == FDG_BASIC_PREACT || p.L[li + 1].kind == FDG_HEAD_PREACT))
-        next_stats = v.sums(p.bns[p.L[li + 1].bn[0]]);
-      FDG_TRY(mconv_forward(m, c2, t_o2, v.W(c2), shortcut, m->S(nxt), v.act(L.out_b), next_stats, s));
-      next_ready = next_stats != nullptr;
-    } else {  // heads
-      const bf16_t* o = cur_b;
-      if (L.kind == FDG_HEAD_PREACT) {
-        const BnInfo& b0 = p.bns[L.bn[0]];
-        if (!stats_ready) FDG_TRY(bn_stats(v, b0, cur_b, s));
-        FDG_TRY(bn_apply(m, v, b0, cur_b, nullptr, nullptr, nullptr, nullptr, v.act(L.act[0]), s));
-        o = v.act(L.act[0]);
-      }
-      const int J = p.d.num_classes;
-      FDG_TRY(launch_avgpool(o, v.pooled(), N, p.head_HW, p.head_C, s));
-      FDG_TRY(launch_fc_fwd(v.pooled(), m->params() + L.fc_w_off, m->params() + L.fc_b_off, v.logits(), N, p.head_C, J, s));
-      FDG_TRY(launch_softmax_ce(v.logits(), v.labels(), y_dev, v.dl(), N, J, s));
-      break;
-    }
-    cur = nxt;
-    cur_b = v.act(L.out_b);
-    stats_ready = next_ready;
-  }
-  if (!p.is_top) FDG_TRY(launch_nhwc_to_nchw(m->S(cur), y_dev, N, p.out_c, p.out_h * p.out_w, p.out_c, s));
+  if (p.replay) FDG_TRY(hipMemcpyAsync(v.xcopy(), x_dev, (size_t)N * p.d.c_in * p.d.h_in * p.d.w_in * 4, hipMemcpyDeviceToDevice, s));
+  if (fdg_status st = forward_pass(m, v, x_dev, y_dev, /*replayed=*/false, s); st != FDG_OK) return st;
   ++m->seq_fwd;
   return FDG_OK;
 }
@@ -736,11 +774,14 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
   if (m->seq_fwd == m->seq_bwd) return FDG_ERR_QUEUE_EMPTY;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   m->last_stream = s;
-  SlotView v{m, m->slot(m->seq_bwd)};  // the OLDEST saved forward
+  SlotView v = view_of(m, m->seq_bwd);  // the OLDEST saved forward
   const int N = p.d.n;
   // the backward sums of batch norm accumulate with atomics and start at zero; every gradient is written
   // (not accumulated) by the kernel that produces it
   FDG_TRY(side_join(m, s));
+  if (p.replay) {   // the saved forward is its input and its weights: run it again into the module's one set of intermediates
+    if (fdg_status st = forward_pass(m, v, v.xcopy(), p.is_top ? m->TP() : nullptr, /*replayed=*/true, s); st != FDG_OK) return st;
+  }
   FDG_TRY(launch_fill_zero(m->ws + p.o_bsums, p.o_running - p.o_bsums, s));
   int cur = 0;
   if (!p.is_top)  // gradient shrinking of Eq. 15: multiply by beta before anything else

@@ -108,9 +108,10 @@ def _split(spec, flat) -> List[Tuple[str, np.ndarray]]:
 
 
 def run_side_by_side(spec, steps: int, seed: int = 0, perturb_bn: bool = True, backward_first: bool = False,
-                     device="cuda:0") -> Tuple[List[Record], List[str]]:
+                     device="cuda:0", save_mode: int = 0) -> Tuple[List[Record], List[str]]:
     """Runs `steps` iterations (after the warm-up that fills the history) on the three runs.
-    Returns (records, exact-check failures)."""
+    Returns (records, exact-check failures).  save_mode is the library's (fdg_save_mode); the oracle runs keep
+    their activations either way: replaying a saved forward changes where the numbers come from, not the numbers."""
     import torch
     from oracle.fdg_oracle import OracleModule
     from paper_1906_09108_amd import FdgModule
@@ -118,7 +119,7 @@ def run_side_by_side(spec, steps: int, seed: int = 0, perturb_bn: bool = True, b
     theta0 = W.make_params(spec, seed, perturb_bn=perturb_bn)
     same = OracleModule(spec, np.float32, storage="bf16")
     plain = OracleModule(spec, np.float32, storage="fp32")
-    gpu = FdgModule(spec, device)
+    gpu = FdgModule(spec, device, save_mode=save_mode)
     for m in (same, plain, gpu):
         m.set_params(theta0)
     records: List[Record] = []

@@ -46,6 +46,33 @@ def test_workspace_bytes_of_benchmark_configs(idx):
     assert binding.fdg_module_workspace_bytes(deeper) > b      # one more ring slot
 
 
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+def test_workspace_bytes_when_a_saved_forward_is_its_input(idx):
+    """FDG_SAVE_INPUT_AND_REPLAY: one set of intermediates for the module instead of one per ring slot; a slot is the
+    weight snapshot plus the fp32 input."""
+    spec = W.config(idx)
+    full = binding.fdg_module_workspace_bytes_ex(spec, binding.FDG_SAVE_ACTIVATIONS)
+    assert full == binding.fdg_module_workspace_bytes(spec)
+    replay = binding.fdg_module_workspace_bytes_ex(spec, binding.FDG_SAVE_INPUT_AND_REPLAY)
+    assert replay > 0 and replay % 256 == 0
+    x_bytes = 4 * spec.n * spec.c_in * spec.h_in * spec.w_in
+    if spec.delay >= 1:
+        assert replay < full
+    else:
+        assert replay <= full + x_bytes + 512          # nothing to share with a single slot: only the input copy is added
+    deeper = W.config(idx)
+    deeper.delay += 1
+    step_full = binding.fdg_module_workspace_bytes(deeper) - full
+    step_replay = binding.fdg_module_workspace_bytes_ex(deeper, binding.FDG_SAVE_INPUT_AND_REPLAY) - replay
+    assert 0 < step_replay < step_full
+    for bad_mode in (-1, 2, 7):
+        assert binding.fdg_module_workspace_bytes_ex(spec, bad_mode) == 0
+    lib = binding.load()
+    out = ctypes.c_void_p()
+    d, keep = binding.make_desc(spec)
+    assert lib.fdg_module_create_ex(ctypes.byref(d), 5, None, 0, None, ctypes.byref(out)) == binding.FDG_ERR_INVALID_ARG
+
+
 def test_invalid_descriptors_are_rejected():
     ok = ModuleSpec(2, 16, 8, 8, [Layer(W.BASIC_POSTACT, 16, 16, 1)])
     assert binding.fdg_module_workspace_bytes(ok) > 0
