@@ -213,7 +213,8 @@ def _postact_stage(c_in: int, c_out: int, blocks: int, first_stride: int) -> Lis
 
 
 def config(idx: int, n: Optional[int] = None) -> ModuleSpec:
-    """Benchmark configuration idx in 1..5.  `n` overrides the batch size (for bounded CPU timing and
+    """Benchmark configuration idx in 1..7 (1..5: the CIFAR modules the metric is stated on; 6, 7: the two halves of
+    ResNet-18 at Tiny-ImageNet resolution, channel counts that are powers of two).  `n` overrides the batch size (for bounded CPU timing and
     small parity cases); everything else keeps its real shape."""
     hyper = dict(momentum=0.9, weight_decay=5e-4, bn_eps=1e-5, bn_momentum=0.1, lr=0.1)
     if idx == 1:
@@ -246,7 +247,18 @@ def config(idx: int, n: Optional[int] = None) -> ModuleSpec:
         ls = [Layer(BASIC_POSTACT, 16, 16, 1) for _ in range(50)] + _postact_stage(16, 32, 100, 2)
         return ModuleSpec(n or 128, 16, 32, 32, ls, delay=2, is_bottom=False, beta=0.2,
                           name="cfg5 ResNet-1202 K=4 module 1 (blocks 150-299)", **hyper)
-    raise ValueError("config index must be 1..5")
+    if idx == 6:
+        # ResNet-18 on Tiny-ImageNet (64x64 images, 200 classes; Table VI), K=2 top module: the upper four of the
+        # eight basic blocks (128->256 stride 2, 256, 256->512 stride 2, 512) + avgpool/FC/softmax-CE.  d=0.
+        ls = _postact_stage(128, 256, 2, 2) + _postact_stage(256, 512, 2, 2) + [Layer(HEAD_POSTACT, 512)]
+        return ModuleSpec(n or 128, 128, 32, 32, ls, delay=0, is_bottom=False, beta=1.0, num_classes=200,
+                          name="cfg6 ResNet-18 Tiny-ImageNet K=2 top module (blocks 5-8 + head)", **hyper)
+    if idx == 7:
+        # the module below it: 3x3 stem 3->64 at 64x64 + blocks 1-4 (64, 64, 64->128 stride 2, 128); beta = 0.5 (Table VI)
+        ls = [Layer(STEM, 3, 64, 1)] + _postact_stage(64, 64, 2, 1) + _postact_stage(64, 128, 2, 2)
+        return ModuleSpec(n or 128, 3, 64, 64, ls, delay=1, is_bottom=True, beta=0.5,
+                          name="cfg7 ResNet-18 Tiny-ImageNet K=2 module 0 (stem + blocks 1-4)", **hyper)
+    raise ValueError("config index must be 1..7")
 
 
 def conv_flops(spec: ModuleSpec) -> int:

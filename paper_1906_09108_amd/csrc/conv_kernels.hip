@@ -158,6 +158,7 @@ hipError_t launch_conv_gather(const GatherConvArgs& a, hipStream_t s) {
     return hipErrorInvalidValue;
   if (conv_gather_wide_applies(a)) return launch_conv_gather_wide(a, s);
   if (a.gate || a.bnx) return hipErrorInvalidValue;   // only the output stage of the wide kernels has them
+  if (conv_narrow_applies(a)) return launch_conv_narrow(a, s);
   if (a.Co <= 16) return run_gather<256, 16, 4, 1>(a, s);
   if (a.Co <= 32) return run_gather<256, 32, 4, 1>(a, s);
   if (a.Co <= 64) return run_gather<128, 64, 2, 2>(a, s);
@@ -345,6 +346,8 @@ hipError_t launch_conv_wgrad(const WgradArgs& a, hipStream_t s) {
   if (conv_wgrad128_applies(a) && !(old_wide && conv_wgrad_wide_applies(a))) return launch_conv_wgrad128(a, s);
   if (conv_wgrad_tall_applies(a) && !(old_wide && conv_wgrad_wide_applies(a))) return launch_conv_wgrad_tall(a, s);
   if (conv_wgrad_wide_applies(a)) return launch_conv_wgrad_wide(a, s);
+  if (conv_wgrad_narrow_applies(a) && a.scratch && a.scratch_bytes >= conv_wgrad_narrow_scratch_bytes(a))
+    return launch_conv_wgrad_narrow(a, s);
   if (a.overwrite) {   // the kernels below only add (atomics)
     hipError_t e = launch_fill_f32(a.dw, (size_t)a.Co * a.ntaps * a.Ci, 0.f, s);
     if (e != hipSuccess) return e;
@@ -478,6 +481,10 @@ size_t conv_wgrad_scratch_bytes(const ConvShape& c) {
   WgradArgs a{};
   a.Co = c.Co; a.Ci = c.Ci; a.Cx = c.Cip; a.OW = c.Wo(); a.ntaps = c.T;
   a.N = c.N; a.OH = c.Ho(); a.Hi = c.Hi; a.Wi = c.Wi; a.stride = c.stride;
+  for (int r = 0; r < 3; ++r)
+    for (int q = 0; q < 3; ++q) a.tap[r * 3 + q] = pack_tap(r - 1, q - 1, 0);
+  a.Cx = c.Cip;
+  if (conv_wgrad_narrow_applies(a)) return conv_wgrad_narrow_scratch_bytes(a);
   if (!(conv_wgrad_wide_applies(a) || conv_wgrad128_applies(a) || conv_wgrad_tall_applies(a))) return 0;
   // room for the partial sums of the pixel splits: 8 of them, or as many as it takes the 160 x 160 kernel to fill
   // the chip when a layer has few blocks (160 -> 160: 9 blocks per filter)

@@ -1,0 +1,453 @@
+// Convolutions of the narrow layers (16, 32 or 64 channels in and out, 3x3, unit stride): the ResNet-56 / -110 /
+// -1202 stages and the first stage of ResNet-18.  Such a layer moves a few megabytes and does a few hundred
+// megaflops per launch, so what a launch costs is the length of the dependent chain inside one workgroup, not the
+// arithmetic: the generic kernel walks the contraction in 32-wide chunks, each chunk a round trip global memory ->
+// registers -> LDS -> barrier, and a filter tap at a time re-reads the pixels nine times.  Here a workgroup
+//   * lands the whole patch of its pixel tile (the tile's pixels with one image row and one pixel on either side,
+//     contiguous in NHWC memory) in LDS with ONE burst of direct-to-LDS loads,
+//   * holds the whole filter in registers as MFMA operand fragments (9 * Ci * Co bf16: 20, 72 or 144 registers per
+//     lane), loaded straight from global memory while the patch is in flight,
+//   * and then runs all MFMAs of its tile from LDS with no further barrier: a filter tap is a shift of the row
+//     index inside the patch, a tap outside the image reads a row of zeros.
+// Same arguments and output stage (store_tile: addend, gated addend, fp32 / bf16 output, batch-norm sums) as the
+// generic gather kernel, so forward and data gradient (flipped taps, transposed filter) both run through it.
+#include "conv_common.h"
+#include <stdio.h>
+#include <stdlib.h>
+
+namespace fdg {
+
+namespace {
+
+__device__ __attribute__((aligned(16))) uint32_t g_narrow_zero[4] = {0u, 0u, 0u, 0u};
+
+__device__ __forceinline__ void narrow_dma16(const void* gsrc, void* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                   (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+}
+
+// CI input channels; a wave owns J blocks of 16 pixels and NB blocks of 16 output channels; WN waves side by side
+// over the output channels (Co = 16 * NB * WN), 4 / WN over the pixels.  LDS: `units` 16-byte units of patch
+// (a multiple of 256: whole load rounds of the workgroup) followed by 128 bytes of zeros.
+template <int CI, int NB, int WN, int J>
+__global__ __launch_bounds__(256) void conv_narrow_kernel(GatherConvArgs a, int units) {
+  constexpr int WM = 4 / WN, TP = 16 * J * WM, CO = 16 * NB * WN;
+  constexpr int U = CI / 8, ROWB = CI * 2;          // 16-byte units and bytes of one pixel
+  constexpr int S = (9 * CI + 31) / 32;             // 32-wide steps of the contraction (taps x channels)
+  constexpr int SWZ_SHIFT = U == 2 ? 2 : (U == 4 ? 1 : 0);   // unit index ^= (row >> SWZ_SHIFT) & (U - 1): b128 reads of 8 consecutive rows hit 8 bank groups
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave % WM, wn = wave / WM;
+  const int W = a.Wi, H = a.Hi;
+  const int Mtot = a.N * H * W;
+  const int m0 = blockIdx.x * TP;
+  const int rows = TP + 2 * W + 2;                   // patch row r holds pixel m0 - W - 1 + r
+
+  // ---- the patch: one burst of loads, lane i of a round lands at unit position base + i ----
+  for (int base = wave * 64; base < units; base += 256) {
+    const int pos = base + lane;
+    const int r = pos / U, us = pos % U;             // stored position -> row and swizzled unit
+    const int u = us ^ ((r >> SWZ_SHIFT) & (U - 1));
+    int q = m0 - W - 1 + r;                          // rows that do not exist read some row that does: nothing valid refers to them
+    q = q < 0 ? 0 : (q >= Mtot ? Mtot - 1 : q);
+    narrow_dma16(a.in + (size_t)q * CI + u * 8, smem + (size_t)base * 16);
+  }
+  if (tid < 8) reinterpret_cast<uint4*>(smem + (size_t)units * 16)[tid] = make_uint4(0u, 0u, 0u, 0u);
+
+  // ---- the filter: fragment (s, nb) = rows 16 nb .. +15 of this wave's channels, k = 32 s + 8 (lane >> 4) .. +7 ----
+  bf16x8 wf[S][NB];
+  {
+    const int g = lane >> 4;
+#pragma unroll
+    for (int s = 0; s < S; ++s)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const int co = (wn * NB + nb) * 16 + (lane & 15);
+        const int k = 32 * s + 8 * g;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (k < 9 * CI && co < a.w_rows) v = *reinterpret_cast<const uint4*>(a.w + (size_t)co * a.Kw + k);
+        wf[s][nb] = __builtin_bit_cast(bf16x8, v);
+      }
+  }
+
+  // ---- LDS address of this lane's pixel fragment for every pixel block and step.  With 64 channels the two steps
+  //      of a tap differ by unit bit 2 = address bit 6 (the zero area is 128 bytes for that), so one address
+  //      serves both ----
+  constexpr int SA = CI == 64 ? 9 : S;
+  const unsigned zero_addr = (unsigned)units * 16u;
+  unsigned xaddr[J][SA];
+  {
+    const int g = lane >> 4;
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+      const int pl = (wm * J + j) * 16 + (lane & 15);
+      const int m = m0 + pl;
+      const bool inside = m < Mtot;
+      const int ow = m % W, oh = (m / W) % H;
+#pragma unroll
+      for (int s = 0; s < SA; ++s) {
+        // which tap and which unit of the pixel this lane's 8 k values are
+        const int slot = CI == 16 ? 2 * s + (g >> 1) : s;
+        const int u = CI == 16 ? (g & 1) : g;
+        unsigned addr = zero_addr;
+        if (slot < 9) {
+          const int tp = a.tap[slot];
+          const int dh = (tp & 0xff) - 8, dw = ((tp >> 8) & 0xff) - 8;
+          const bool ok = inside && (unsigned)(oh + dh) < (unsigned)H && (unsigned)(ow + dw) < (unsigned)W;
+          const int r = pl + W + 1 + dh * W + dw;
+          if (ok) addr = (unsigned)(r * ROWB + ((u ^ ((r >> SWZ_SHIFT) & (U - 1))) << 4));
+        }
+        xaddr[j][s] = addr;
+      }
+    }
+  }
+
+  f32x4 acc[NB][J];
+#pragma unroll
+  for (int i = 0; i < NB; ++i)
+#pragma unroll
+    for (int j = 0; j < J; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  __builtin_amdgcn_s_waitcnt(0);   // every load of this wave has landed (patch in LDS, filter in registers)
+  __syncthreads();
+
+#pragma unroll
+  for (int j = 0; j < J; ++j)
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+      const unsigned addr = CI == 64 ? (xaddr[j][s >> 1] ^ ((s & 1) << 6)) : xaddr[j][s];
+      const bf16x8 b = *reinterpret_cast<const bf16x8*>(smem + addr);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) acc[nb][j] = mfma16(wf[s][nb], b, acc[nb][j]);
+    }
+
+  (void)rows;
+  store_tile<J, NB, CO>(a, acc, m0 + wm * J * 16, 0, wn * NB * 16, lane);
+}
+
+template <int CI, int NB, int WN, int J>
+hipError_t run_narrow(const GatherConvArgs& a, hipStream_t s) {
+  constexpr int WM = 4 / WN, TP = 16 * J * WM, U = CI / 8;
+  const int Mtot = a.N * a.OH * a.OW;
+  const int rows = TP + 2 * a.Wi + 2;
+  const int units = (rows * U + 255) / 256 * 256;
+  const size_t lds = (size_t)units * 16 + 128;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_narrow_kernel<CI, NB, WN, J>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  static char name[64];
+  if (!name[0]) snprintf(name, sizeof(name), "conv_narrow_kernel<%d, %d, %d, %d>", CI, NB, WN, J);
+  note_kernel(name);
+  hipLaunchKernelGGL((conv_narrow_kernel<CI, NB, WN, J>), dim3((Mtot + TP - 1) / TP), dim3(256), lds, s, a, units);
+  return hipGetLastError();
+}
+
+// pixel blocks per wave: the largest of 4, 2, 1 that still leaves two workgroups per compute unit
+template <int CI, int NB, int WN>
+hipError_t run_narrow_j(const GatherConvArgs& a, hipStream_t s) {
+  constexpr int WM = 4 / WN;
+  const int Mtot = a.N * a.OH * a.OW;
+  if (Mtot >= 512 * 64 * WM) return run_narrow<CI, NB, WN, 4>(a, s);
+  if (Mtot >= 512 * 32 * WM) return run_narrow<CI, NB, WN, 2>(a, s);
+  return run_narrow<CI, NB, WN, 1>(a, s);
+}
+
+
+// ------------------------------------------------------------------------------------------------
+// Weight gradient of the same layers: dw[co, tap, ci] = sum over pixels of dy[pixel, co] * x[pixel + tap, ci]
+// ------------------------------------------------------------------------------------------------
+// The contraction runs over pixels and the result is tiny (C x 9 x C), so the generic kernel's split (one filter tap
+// and one range of pixels per workgroup, fp32 atomics into dw after a fill kernel) reads x nine times and ends in
+// hundreds of atomics per address.  Here a workgroup owns a range of image rows for ALL nine taps:
+//   * x and dy of those rows land in LDS once, in a PADDED layout: every image row has a zero pixel on either side
+//     and every image a zero row above and below (lanes whose destination is padding load the zero word).  A tap is
+//     then a constant shift of the position index with no masking: what a shifted read picks up beyond the image
+//     is a stored zero, and positions that are padding in dy contribute nothing;
+//   * the operands are read with the transposing LDS load (8 pixels of one channel per lane) and every wave keeps
+//     the whole [16 co][9 taps][C ci] block of its output-channel block in registers;
+//   * waves that share an output-channel block split the pixel steps and add their blocks through LDS; the
+//     workgroup's sum goes to its own slice of a scratch array, and a second kernel adds the slices.
+struct NarrowWgradLaunch {
+  int R;            // padded rows per tile
+  int tiles;        // tiles in all; workgroup b takes tiles b, b + gridDim.x, ...
+  int PW, HP;       // padded row length W + 2 and padded image height H + 2
+  int rows_total;   // N * HP
+  int KP;           // positions a workgroup contracts over: R * PW rounded up to 32
+  int xunits, dyunits;   // 16-byte units of the two LDS regions (multiples of 256)
+  float* partial;
+  size_t stride;    // floats per slice
+};
+
+typedef short n_v4s16 __attribute__((ext_vector_type(4)));
+// One operand fragment = two transposing reads (pixels 4g .. 4g+3 and 16 more rows further).  The reads are inline
+// assembly without a wait, so that a whole batch is in flight before the first use: narrow_frags_landed() waits
+// once, narrow_join() ties the registers to that wait (volatile statements keep their order).
+struct NarrowFrag { n_v4s16 lo, hi; };
+__device__ __forceinline__ void narrow_read_tr8(NarrowFrag& f, unsigned addr, unsigned second) {
+  asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(f.lo) : "v"(addr));
+  asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(f.hi) : "v"(addr + second));
+}
+__device__ __forceinline__ void narrow_frags_landed() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ bf16x8 narrow_join(NarrowFrag& f) {
+  asm volatile("" : "+v"(f.lo), "+v"(f.hi));
+  typedef short v8s16 __attribute__((ext_vector_type(8)));
+  const v8s16 both = __builtin_shufflevector(f.lo, f.hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, both);
+}
+
+template <int C>
+__global__ __launch_bounds__(256) void conv_wgrad_narrow_kernel(WgradArgs a, NarrowWgradLaunch L) {
+  constexpr int U = C / 8, ROWB = C * 2, NCB = C / 16, WK = 4 / NCB;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wcb = wave % NCB, wk = wave / NCB;
+  const int W = a.Wi, H = a.Hi, PW = L.PW, HP = L.HP;
+  const char* zero = reinterpret_cast<const char*>(g_narrow_zero);
+
+  // position idx of a region -> source pixel.  x region: idx 0 is one position before padded row pr0 - 1;
+  // dy region: idx 0 is the first position of padded row pr0.  With 64 channels the 32-byte slot of a position is
+  // XORed with bit 1 of idx (the four pixels of a transposing read then fall into four bank groups).
+  int pr0 = 0;                                       // first padded row (over all images) of the current tile
+  auto fill = [&](const bf16_t* src, int units, int lead, int first_row, int nrows, int lds_unit0) {
+    for (int base = wave * 64; base < units; base += 256) {
+      const int pos = base + lane;
+      const int idx = pos / U, us = pos % U;
+      const int u = C == 64 ? (us ^ ((idx & 2) << 1)) : us;
+      const int xp = idx - lead;
+      const int lr = xp >= 0 ? xp / PW : -1;
+      const int c = xp - lr * PW;
+      const int gr = first_row + lr;
+      const int n = gr >= 0 ? gr / HP : 0;
+      const int hr = gr - n * HP;
+      const bool ok = lr >= 0 && lr < nrows && gr >= 0 && gr < L.rows_total && hr >= 1 && hr <= H && c >= 1 && c <= W;
+      const char* g = reinterpret_cast<const char*>(src + (((size_t)n * H + (hr - 1)) * W + (c - 1)) * C + u * 8);
+      narrow_dma16(ok ? g : zero, smem + (size_t)(lds_unit0 + base) * 16);
+    }
+  };
+  f32x4 acc[9][NCB];
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int j = 0; j < NCB; ++j) acc[t][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  int shift[9];   // x idx of a tap relative to the dy position
+#pragma unroll
+  for (int t = 0; t < 9; ++t) {
+    const int dh = (a.tap[t] & 0xff) - 8, dw = ((a.tap[t] >> 8) & 0xff) - 8;
+    shift[t] = 1 + (1 + dh) * PW + dw;
+  }
+
+  const int g = lane >> 4, i16 = lane & 15;
+  const unsigned dy0 = (unsigned)L.xunits * 16u;
+  constexpr int TB = C == 16 ? 9 : 3;                // taps whose fragments are read in one batch
+  for (int tile = blockIdx.x; tile < L.tiles; tile += gridDim.x) {
+    if (tile != (int)blockIdx.x) __syncthreads();      // every wave is done reading the previous tile
+    pr0 = tile * L.R;
+    fill(a.x, L.xunits, 1, pr0 - 1, L.R + 2, 0);
+    fill(a.dy, L.dyunits, 0, pr0, L.R, L.xunits);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    for (int st = wk; st < L.KP / 32; st += WK) {
+      const int pp = st * 32 + 4 * g + (i16 >> 2);     // this lane's first pixel position of the step
+      const int aslot = C == 64 ? (wcb ^ (pp & 2)) : wcb;
+      NarrowFrag ra;
+      narrow_read_tr8(ra, dy0 + (unsigned)(pp * ROWB + aslot * 32 + (i16 & 3) * 8), 16 * ROWB);
+      bf16x8 fa;
+#pragma unroll
+      for (int t0 = 0; t0 < 9; t0 += TB) {
+        NarrowFrag rb[TB][NCB];
+#pragma unroll
+        for (int t = 0; t < TB; ++t) {
+          const int idx = pp + shift[t0 + t];
+#pragma unroll
+          for (int j = 0; j < NCB; ++j) {
+            const int bslot = C == 64 ? (j ^ (idx & 2)) : j;
+            narrow_read_tr8(rb[t][j], (unsigned)(idx * ROWB + bslot * 32 + (i16 & 3) * 8), 16 * ROWB);
+          }
+        }
+        narrow_frags_landed();
+        if (t0 == 0) fa = narrow_join(ra);
+#pragma unroll
+        for (int t = 0; t < TB; ++t)
+#pragma unroll
+          for (int j = 0; j < NCB; ++j) acc[t0 + t][j] = mfma16(fa, narrow_join(rb[t][j]), acc[t0 + t][j]);
+      }
+    }
+  }
+
+  // ---- add the blocks of the waves that share an output-channel block, then store the workgroup's slice ----
+  if (WK > 1) {
+    __syncthreads();   // every wave is done with the tiles
+    float4* red = reinterpret_cast<float4*>(smem);
+    if (wk > 0) {
+#pragma unroll
+      for (int t = 0; t < 9; ++t)
+#pragma unroll
+        for (int j = 0; j < NCB; ++j)
+          red[(((wk - 1) * NCB + wcb) * 9 * NCB + t * NCB + j) * 64 + lane] = make_float4(acc[t][j][0], acc[t][j][1], acc[t][j][2], acc[t][j][3]);
+    }
+    __syncthreads();
+    if (wk == 0) {
+      for (int o = 1; o < WK; ++o)
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+#pragma unroll
+          for (int j = 0; j < NCB; ++j) {
+            const float4 v = red[(((o - 1) * NCB + wcb) * 9 * NCB + t * NCB + j) * 64 + lane];
+            acc[t][j][0] += v.x; acc[t][j][1] += v.y; acc[t][j][2] += v.z; acc[t][j][3] += v.w;
+          }
+    }
+  }
+  if (wk == 0) {
+    float* out = L.partial + (size_t)blockIdx.x * L.stride;
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+#pragma unroll
+      for (int j = 0; j < NCB; ++j)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int co = wcb * 16 + 4 * g + v, ci = j * 16 + i16;
+          out[((size_t)co * 9 + t) * C + ci] = acc[t][j][v];
+        }
+    }
+  }
+}
+
+// dw (+)= sum of the slices: a block owns 16 float4 of the result, 16 thread groups take every 16th slice each
+__global__ __launch_bounds__(256) void wgrad_slices_reduce_kernel(float4* __restrict__ dw, const float4* __restrict__ partial,
+                                                                  int n4, int slices, size_t stride4, int overwrite) {
+  __shared__ float4 red[256];
+  const int i = blockIdx.x * 16 + (threadIdx.x & 15), grp = threadIdx.x >> 4;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (i < n4) {
+#pragma unroll 4
+    for (int k = grp; k < slices; k += 16) {
+      const float4 p = partial[(size_t)k * stride4 + i];
+      s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+    }
+  }
+  red[threadIdx.x] = s;
+  __syncthreads();
+  if (grp == 0 && i < n4) {
+    float4 t = overwrite ? make_float4(0.f, 0.f, 0.f, 0.f) : dw[i];
+    for (int k = 0; k < 16; ++k) {
+      const float4 p = red[k * 16 + (threadIdx.x & 15)];
+      t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
+    }
+    dw[i] = t;
+  }
+}
+
+struct NarrowWgradPlan { NarrowWgradLaunch L; int blocks; size_t lds; };
+
+// tile height: about one tile per compute unit, within 96 KB of LDS; at most 256 workgroups (and slices)
+bool plan_wgrad_narrow(const WgradArgs& a, NarrowWgradPlan& P) {
+  const int C = a.Co, U = C / 8, ROWB = C * 2;
+  const int PW = a.Wi + 2, HP = a.Hi + 2;
+  const long long rows_total = (long long)a.N * HP;
+  if (rows_total * PW >= (1ll << 30)) return false;
+  int R = (int)((rows_total + 255) / 256);
+  if (R < 1) R = 1;
+  for (;; --R) {
+    const int KP = (R * PW + 31) / 32 * 32;
+    const int xpos = KP + 2 * PW + 2, xunits = (xpos * U + 255) / 256 * 256, dyunits = (KP * U + 255) / 256 * 256;
+    const size_t tiles = (size_t)(xunits + dyunits) * 16;
+    const size_t red = C == 64 ? 0 : (size_t)3 * 9 * (C / 16) * 1024;   // blocks of the waves that are added
+    if (tiles <= 96 * 1024 || R == 1) {
+      if (tiles > 96 * 1024) return false;
+      P.L.R = R; P.L.PW = PW; P.L.HP = HP; P.L.rows_total = (int)rows_total; P.L.KP = KP;
+      P.L.xunits = xunits; P.L.dyunits = dyunits;
+      P.L.tiles = (int)((rows_total + R - 1) / R);
+      P.blocks = P.L.tiles < 256 ? P.L.tiles : 256;
+      P.lds = tiles > red ? tiles : red;
+      (void)ROWB;
+      return true;
+    }
+  }
+}
+
+}  // namespace
+
+bool conv_narrow_applies(const GatherConvArgs& a) {
+  static const bool off = getenv("FDG_NO_NARROW") != nullptr || getenv("FDG_NO_NARROW_CONV") != nullptr;   // A/B switch for measurements
+  if (off) return false;
+  if (a.Ci != 16 && a.Ci != 32 && a.Ci != 64) return false;
+  if (a.Co != a.Ci || a.w_rows != a.Co || a.Kw != 9 * a.Ci) return false;
+  if (a.ntaps != 9 || a.in_stride != 1 || a.out_stride != 1 || a.ooh != 0 || a.oow != 0 || a.nclass > 1) return false;
+  if (a.OH != a.Hi || a.OW != a.Wi || a.OHf != a.OH || a.OWf != a.OW || a.Wi < 1) return false;
+  if (a.gate || a.bnx) return false;
+  if ((long long)a.N * a.Hi * a.Wi >= (1ll << 30)) return false;
+  for (int i = 0; i < 9; ++i) {
+    const int dh = (a.tap[i] & 0xff) - 8, dw = ((a.tap[i] >> 8) & 0xff) - 8;
+    if (dh < -1 || dh > 1 || dw < -1 || dw > 1 || (a.tap[i] >> 16) != i) return false;
+  }
+  // the patch of the largest tile in LDS (two workgroups per compute unit at least)
+  const int tp_max = a.Ci == 64 ? 128 : 256;
+  if (((size_t)(tp_max + 2 * a.Wi + 2) * (a.Ci / 8) + 256) * 16 > 64 * 1024) return false;
+  return true;
+}
+
+hipError_t launch_conv_narrow(const GatherConvArgs& a, hipStream_t s) {
+  if (!conv_narrow_applies(a) || a.N * a.OH * a.OW <= 0) return hipErrorInvalidValue;
+  if (a.Ci == 16) return run_narrow_j<16, 1, 1>(a, s);
+  if (a.Ci == 32) return run_narrow_j<32, 2, 1>(a, s);
+  return run_narrow_j<64, 2, 2>(a, s);
+}
+
+bool conv_wgrad_narrow_applies(const WgradArgs& a) {
+  static const bool off = getenv("FDG_NO_NARROW") != nullptr || getenv("FDG_NO_NARROW_WGRAD") != nullptr;   // A/B switch for measurements
+  if (off) return false;
+  if (a.Co != 16 && a.Co != 32 && a.Co != 64) return false;
+  if (a.Ci != a.Co || a.Cx != a.Co || a.ntaps != 9 || a.stride != 1 || a.OH != a.Hi || a.OW != a.Wi) return false;
+  for (int i = 0; i < 9; ++i) {
+    const int dh = (a.tap[i] & 0xff) - 8, dw = ((a.tap[i] >> 8) & 0xff) - 8;
+    if (dh < -1 || dh > 1 || dw < -1 || dw > 1) return false;
+  }
+  NarrowWgradPlan P;
+  return plan_wgrad_narrow(a, P);
+}
+
+size_t conv_wgrad_narrow_scratch_bytes(const WgradArgs& a) {
+  NarrowWgradPlan P;
+  if (!conv_wgrad_narrow_applies(a) || !plan_wgrad_narrow(a, P)) return 0;
+  return (size_t)P.blocks * a.Co * 9 * a.Ci * 4;
+}
+
+template <int C>
+static hipError_t run_wgrad_narrow(const WgradArgs& a, const NarrowWgradPlan& P, hipStream_t s) {
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad_narrow_kernel<C>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  static char name[64];
+  if (!name[0]) snprintf(name, sizeof(name), "conv_wgrad_narrow_kernel<%d>", C);
+  note_kernel(name);
+  hipLaunchKernelGGL((conv_wgrad_narrow_kernel<C>), dim3(P.blocks), dim3(256), P.lds, s, a, P.L);
+  return hipGetLastError();
+}
+
+hipError_t launch_conv_wgrad_narrow(const WgradArgs& a, hipStream_t s) {
+  NarrowWgradPlan P;
+  if (!conv_wgrad_narrow_applies(a) || !plan_wgrad_narrow(a, P)) return hipErrorInvalidValue;
+  const size_t n = (size_t)a.Co * 9 * a.Ci;
+  if (!a.scratch || a.scratch_bytes < (size_t)P.blocks * n * 4) return hipErrorInvalidValue;
+  P.L.partial = a.scratch;
+  P.L.stride = n;
+  hipError_t e = a.Co == 16 ? run_wgrad_narrow<16>(a, P, s) : (a.Co == 32 ? run_wgrad_narrow<32>(a, P, s) : run_wgrad_narrow<64>(a, P, s));
+  if (e != hipSuccess) return e;
+  const int n4 = (int)(n / 4);
+  hipLaunchKernelGGL(wgrad_slices_reduce_kernel, dim3((n4 + 15) / 16), dim3(256), 0, s, reinterpret_cast<float4*>(a.dw),
+                     reinterpret_cast<const float4*>(a.scratch), n4, P.blocks, n / 4, a.overwrite);
+  return hipGetLastError();
+}
+
+}  // namespace fdg

@@ -48,6 +48,9 @@ struct GatherConvArgs {
   int ctap[4][4];
 };
 hipError_t launch_conv_gather(const GatherConvArgs& a, hipStream_t s);
+// narrow layers (16 / 32 / 64 channels in and out, 3x3, unit stride): whole patch and whole filter on chip
+bool conv_narrow_applies(const GatherConvArgs& a);
+hipError_t launch_conv_narrow(const GatherConvArgs& a, hipStream_t s);
 
 // dw[co, tap, ci] += sum_m dy[m, co] * x[pixel(m, tap), ci]   (fp32 atomics; dw must be pre-zeroed)
 struct WgradArgs {
@@ -64,6 +67,11 @@ struct WgradArgs {
   int overwrite;     // 1: dw = sum (no need to zero dw first);  0: dw += sum
 };
 hipError_t launch_conv_wgrad(const WgradArgs& a, hipStream_t s);
+// narrow layers (16 / 32 / 64 channels in and out, 3x3, unit stride): all nine taps of a range of image rows per
+// workgroup, per-workgroup slices in a.scratch added by a second kernel
+bool conv_wgrad_narrow_applies(const WgradArgs& a);
+size_t conv_wgrad_narrow_scratch_bytes(const WgradArgs& a);
+hipError_t launch_conv_wgrad_narrow(const WgradArgs& a, hipStream_t s);
 
 // One convolution of a module: 3x3 with padding 1 (T = 9) or 1x1 with padding 0 (T = 1), stride 1 or 2.
 // Activations carry Cip = Ci rounded up to 8 channels (the padding channels hold zeros).

