@@ -28,7 +28,8 @@ __device__ __forceinline__ float bf16_hi(uint32_t u) { return __builtin_bit_cast
 
 // Output stage of a gather-form convolution.  acc[i][j] is the 16x16 result block of channel group i
 // and pixel group j of this wave: lane l holds channels 4*(l>>4) .. +3 of pixel (l & 15).  Adds the
-// optional fp32 addend (gated by addmask > 0 when given) and writes fp32 and/or bf16.
+// optional fp32 addend (gated by addmask > 0 when given), applies the optional gate, writes fp32 and/or bf16 and
+// adds the per-channel sums (of the bf16 output and its square, or with bnx of the output and output * bnx).
 // BN = channels of the workgroup tile starting at c_tile; this wave's channels start at c_tile + c_wave.
 // Must be called by all threads of the workgroup (the statistics are combined through LDS).
 template <int FM, int FN, int BN>
@@ -67,13 +68,28 @@ __device__ __forceinline__ void store_tile(const GatherConvArgs& a, const f32x4 
         v[2] += ad.z;
         v[3] += ad.w;
       }
+      if (a.gate) {   // data gradient that ends in a ReLU: kept where the ReLU's output was positive
+        const uint2 gt = *reinterpret_cast<const uint2*>(a.gate + o);
+        if (!(bf16_lo(gt.x) > 0.f)) v[0] = 0.f;
+        if (!(bf16_hi(gt.x) > 0.f)) v[1] = 0.f;
+        if (!(bf16_lo(gt.y) > 0.f)) v[2] = 0.f;
+        if (!(bf16_hi(gt.y) > 0.f)) v[3] = 0.f;
+      }
       if (a.out_f32) *reinterpret_cast<float4*>(a.out_f32 + o) = make_float4(v[0], v[1], v[2], v[3]);
       const uint2 packed = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
       if (a.out_b16) *reinterpret_cast<uint2*>(a.out_b16 + o) = packed;
       if (a.stats) {
-        const float r0 = bf16_lo(packed.x), r1 = bf16_hi(packed.x), r2 = bf16_lo(packed.y), r3 = bf16_hi(packed.y);
+        const bool f = a.stats_f32 != 0;
+        const float r0 = f ? v[0] : bf16_lo(packed.x), r1 = f ? v[1] : bf16_hi(packed.x);
+        const float r2 = f ? v[2] : bf16_lo(packed.y), r3 = f ? v[3] : bf16_hi(packed.y);
         s1[i][0] += r0; s1[i][1] += r1; s1[i][2] += r2; s1[i][3] += r3;
-        s2[i][0] += r0 * r0; s2[i][1] += r1 * r1; s2[i][2] += r2 * r2; s2[i][3] += r3 * r3;
+        if (a.bnx) {   // the two sums of the batch-norm backward that follows: sum g and sum g * x
+          const uint2 bx = *reinterpret_cast<const uint2*>(a.bnx + o);
+          s2[i][0] += r0 * bf16_lo(bx.x); s2[i][1] += r1 * bf16_hi(bx.x);
+          s2[i][2] += r2 * bf16_lo(bx.y); s2[i][3] += r3 * bf16_hi(bx.y);
+        } else {
+          s2[i][0] += r0 * r0; s2[i][1] += r1 * r1; s2[i][2] += r2 * r2; s2[i][3] += r3 * r3;
+        }
       }
     }
   }

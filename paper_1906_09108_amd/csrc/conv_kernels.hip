@@ -157,8 +157,8 @@ hipError_t launch_conv_gather(const GatherConvArgs& a, hipStream_t s) {
   if (a.Ci % 8 != 0 || a.Co % 4 != 0 || a.ntaps < 0 || a.ntaps > 9 || a.N * a.OH * a.OW <= 0 || a.Kw % 8 != 0)
     return hipErrorInvalidValue;
   if (conv_gather_wide_applies(a)) return launch_conv_gather_wide(a, s);
-  if (a.gate || a.bnx) return hipErrorInvalidValue;   // only the output stage of the wide kernels has them
   if (conv_narrow_applies(a)) return launch_conv_narrow(a, s);
+  if (a.gate || a.bnx) return hipErrorInvalidValue;   // the generic kernel is not asked for them (conv_dgrad_gates)
   if (a.Co <= 16) return run_gather<256, 16, 4, 1>(a, s);
   if (a.Co <= 32) return run_gather<256, 32, 4, 1>(a, s);
   if (a.Co <= 64) return run_gather<128, 64, 2, 2>(a, s);
@@ -380,18 +380,37 @@ hipError_t conv_forward(const ConvShape& c, const bf16_t* x, const bf16_t* w, co
 
 static hipError_t conv_dgrad_impl(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                                   const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, float* gsums, float* out_f32,
-                                  bf16_t* out_b16, hipStream_t s);
+                                  bf16_t* out_b16, hipStream_t s, bool stats_f32 = false);
 
 hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                       const bf16_t* addmask, float* out_f32, bf16_t* out_b16, hipStream_t s) {
   return conv_dgrad_impl(c, dy, wt, addend, addmask, nullptr, nullptr, nullptr, out_f32, out_b16, s);
 }
 
-// The gate and the sums live in the output stage of the wide kernels; every launch of this data gradient must be one.
+// the narrow kernel runs the whole data gradient of this layer
+bool conv_dgrad_feeds_next(const ConvShape& c) {
+  if (c.stride != 1 || c.T != 9) return false;
+  GatherConvArgs a{};
+  a.N = c.N; a.Hi = c.Ho(); a.Wi = c.Wo(); a.Ci = c.Co; a.Co = c.Cip; a.w_rows = c.Cip; a.Kw = c.T * c.Co;
+  a.OH = c.Hi; a.OW = c.Wi; a.OHf = c.Hi; a.OWf = c.Wi; a.in_stride = 1; a.out_stride = 1; a.ntaps = 9;
+  for (int r = 0; r < 3; ++r)
+    for (int q = 0; q < 3; ++q) a.tap[r * 3 + q] = pack_tap(1 - r, 1 - q, r * 3 + q);
+  return conv_narrow_applies(a);
+}
+
+hipError_t conv_dgrad_feeding_next(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
+                                   const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, float* gsums, float* out_f32,
+                                   bf16_t* out_b16, hipStream_t s) {
+  if (!gate || !bnx || !gsums || !out_f32 || !conv_dgrad_feeds_next(c)) return hipErrorInvalidValue;
+  return conv_dgrad_impl(c, dy, wt, addend, addmask, gate, bnx, gsums, out_f32, out_b16, s, /*stats_f32=*/true);
+}
+
+// The gate and the sums are taken where the wide kernels or the narrow kernel run the whole data gradient.
 bool conv_dgrad_gates(const ConvShape& c) {
   GatherConvArgs a{};
   a.Hi = c.Ho(); a.Wi = c.Wo(); a.Ci = c.Co; a.Co = c.Cip; a.Kw = c.T * c.Co; a.ntaps = 1;
-  return conv_gather_wide_applies(a) && (c.stride == 1 || (c.Hi >= 2 && c.Wi >= 2));
+  if (conv_gather_wide_applies(a) && (c.stride == 1 || (c.Hi >= 2 && c.Wi >= 2))) return true;
+  return conv_dgrad_feeds_next(c);
 }
 
 hipError_t conv_dgrad_gated(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend, const bf16_t* gate,
@@ -402,10 +421,10 @@ hipError_t conv_dgrad_gated(const ConvShape& c, const bf16_t* dy, const bf16_t* 
 
 static hipError_t conv_dgrad_impl(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                                   const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, float* gsums, float* out_f32,
-                                  bf16_t* out_b16, hipStream_t s) {
+                                  bf16_t* out_b16, hipStream_t s, bool stats_f32) {
   GatherConvArgs a{};
   a.in = dy; a.w = wt; a.addend = addend; a.addmask = addmask; a.out_f32 = out_f32; a.out_b16 = out_b16;
-  a.gate = gate; a.bnx = bnx; a.stats = gsums;
+  a.gate = gate; a.bnx = bnx; a.stats = gsums; a.stats_f32 = stats_f32 ? 1 : 0;
   a.N = c.N; a.Hi = c.Ho(); a.Wi = c.Wo(); a.Ci = c.Co;
   a.in_stride = 1;
   a.OHf = c.Hi; a.OWf = c.Wi;

@@ -9,8 +9,8 @@
 //     lane), loaded straight from global memory while the patch is in flight,
 //   * and then runs all MFMAs of its tile from LDS with no further barrier: a filter tap is a shift of the row
 //     index inside the patch, a tap outside the image reads a row of zeros.
-// Same arguments and output stage (store_tile: addend, gated addend, fp32 / bf16 output, batch-norm sums) as the
-// generic gather kernel, so forward and data gradient (flipped taps, transposed filter) both run through it.
+// Same arguments and output stage (store_tile: addend, gated addend, ReLU gate, fp32 / bf16 output, batch-norm sums
+// of the forward or of the backward that follows) as the generic gather kernel, so forward and data gradient (flipped taps, transposed filter) both run through it.
 #include "conv_common.h"
 #include <stdio.h>
 #include <stdlib.h>
@@ -381,7 +381,6 @@ bool conv_narrow_applies(const GatherConvArgs& a) {
   if (a.Co != a.Ci || a.w_rows != a.Co || a.Kw != 9 * a.Ci) return false;
   if (a.ntaps != 9 || a.in_stride != 1 || a.out_stride != 1 || a.ooh != 0 || a.oow != 0 || a.nclass > 1) return false;
   if (a.OH != a.Hi || a.OW != a.Wi || a.OHf != a.OH || a.OWf != a.OW || a.Wi < 1) return false;
-  if (a.gate || a.bnx) return false;
   if ((long long)a.N * a.Hi * a.Wi >= (1ll << 30)) return false;
   for (int i = 0; i < 9; ++i) {
     const int dh = (a.tap[i] & 0xff) - 8, dw = ((a.tap[i] >> 8) & 0xff) - 8;

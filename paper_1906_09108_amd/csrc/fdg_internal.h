@@ -30,6 +30,7 @@ struct GatherConvArgs {
   const bf16_t* gate;    // optional (output indexing): the output is kept where gate > 0 and is zero elsewhere
   const bf16_t* bnx;     // optional (output indexing), with stats: stats[Co + c] += sum of output * bnx instead of
                          // the squares -- with stats[c] the two sums the batch-norm backward needs
+  int stats_f32;         // with bnx, narrow / generic output stage: the sums are of the fp32 values, not of the bf16 output
   int N, Hi, Wi, Ci;
   int OH, OW, in_stride;
   int OHf, OWf, out_stride, ooh, oow;
@@ -91,6 +92,12 @@ hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, co
 // The same, ending in the gate of the ReLU below and the two sums of the batch norm below it:
 //   dx = gate > 0 ? dgrad + addend : 0;  gsums[c] += sum bf16(dx[.., c]);  gsums[Cip + c] += sum bf16(dx[.., c]) * bnx[.., c].
 // Only where conv_dgrad_gates(c) (the wide kernels); hipErrorInvalidValue otherwise.
+// The narrow kernel runs this data gradient, so its fp32 result can be gated by the output of the layer below and
+// carry the two sums of that layer's last batch norm (conv_dgrad_feeding_next).
+bool conv_dgrad_feeds_next(const ConvShape& c);
+hipError_t conv_dgrad_feeding_next(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
+                                   const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, float* gsums, float* out_f32,
+                                   bf16_t* out_b16, hipStream_t s);
 bool conv_dgrad_gates(const ConvShape& c);
 hipError_t conv_dgrad_gated(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend, const bf16_t* gate,
                             const bf16_t* bnx, float* gsums, float* out_f32, bf16_t* out_b16, hipStream_t s);

@@ -570,6 +570,23 @@ hipError_t bn_backward_after_gated_dgrad(const fdg_module* m, const SlotView& v,
   return launch_bn_bwd_apply(a, s);
 }
 
+// The same for an fp32 gradient that the data gradient of the layer above left gated, with the two sums taken from
+// the fp32 values (conv_dgrad_feeding_next).
+hipError_t bn_backward_fed_from_above(const fdg_module* m, const SlotView& v, const BnInfo& b, const float* g, const bf16_t* x,
+                                      bf16_t* out_b16, hipStream_t s) {
+  BnBwdArgs a{};
+  a.dy = g; a.dy_is_f32 = 1; a.mask = nullptr; a.x = x; a.sums = v.sums(b);
+  a.gamma = v.snap(b.gamma_off);
+  a.bsums = m->bsums() + b.stat_off;
+  a.out_b16 = out_b16;
+  a.dgamma = m->grads() + b.gamma_off; a.dbeta = m->grads() + b.beta_off;
+  a.M = b.M; a.C = b.C; a.eps = m->p.d.bn_eps;
+  a.dy_gated = 1; a.raw_sums = 1;
+  if (hipError_t e = side_wait_readers(m, out_b16, s); e != hipSuccess) return e;
+  ProfScope ps(m, PC_BN_BWD, 0, (double)b.M * b.C * (4 + 2 + 2), s);
+  return launch_bn_bwd_apply(a, s);
+}
+
 // Data gradient of convolution c into g (bf16), then the backward of the ReLU (gate = its output) and of the batch
 // norm b (input x) that precede the convolution.  Where the wide kernels run, the gate and the two sums of the
 // batch-norm backward are taken in the data gradient's output stage and one pass over g is saved.
@@ -786,11 +803,16 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
   int cur = 0;
   if (!p.is_top)  // gradient shrinking of Eq. 15: multiply by beta before anything else
     FDG_TRY(launch_nchw_to_nhwc(grad_out_dev, m->G(cur), m->GB(cur), N, p.out_c, p.out_h * p.out_w, p.out_c, p.d.beta, s));
+  static const bool no_feed = getenv("FDG_NO_GATED_DGRAD") != nullptr;   // A/B switch for measurements
+  bool fed = false;   // G(cur) came from the layer above already gated by this layer's output, with this layer's
+                      // last batch norm's two sums in bsums
   for (int li = (int)p.L.size() - 1; li >= 0; --li) {
     const LayerPlan& L = p.L[li];
     const int nxt = cur ^ 1;
     const bf16_t* in_b = li == 0 ? v.xin() : v.act(p.L[li - 1].out_b);  // bf16 copy of this layer's input
     const bool need_dx = !(li == 0 && p.d.is_bottom);
+    const bool fed_here = fed;
+    fed = false;
     if (L.kind == FDG_HEAD_POSTACT || L.kind == FDG_HEAD_PREACT) {
       const int J = p.d.num_classes;
       float* dp = reinterpret_cast<float*>(m->ws + p.o_dp);
@@ -807,7 +829,8 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
     } else if (L.kind == FDG_STEM_CONV_BN_RELU) {
       const ConvInfo& c0 = p.convs[L.conv[0]];
       const BnInfo& b0 = p.bns[L.bn[0]];
-      FDG_TRY(bn_backward(m, v, b0, m->G(cur), true, v.act(L.out_b), v.act(L.act[0]), nullptr, nullptr, m->T(0), s));
+      if (fed_here) FDG_TRY(bn_backward_fed_from_above(m, v, b0, m->G(cur), v.act(L.act[0]), m->T(0), s));
+      else FDG_TRY(bn_backward(m, v, b0, m->G(cur), true, v.act(L.out_b), v.act(L.act[0]), nullptr, nullptr, m->T(0), s));
       FDG_TRY(mconv_wgrad(m, c0, in_b, m->T(0), s));
       if (need_dx) FDG_TRY(mconv_dgrad(m, c0, m->T(0), v.Wt(c0), nullptr, nullptr, m->G(nxt), m->GB(nxt), s));
     } else if (L.kind == FDG_BASIC_POSTACT) {
@@ -815,7 +838,8 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
       const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]];
       const bf16_t *t_c1 = v.act(L.act[0]), *t_a1 = v.act(L.act[1]), *t_c2 = v.act(L.act[2]), *t_y = v.act(L.out_b);
       // final ReLU mask (y > 0) then BN2
-      FDG_TRY(bn_backward(m, v, b2, m->G(cur), true, t_y, t_c2, nullptr, nullptr, m->T(0), s));
+      if (fed_here) FDG_TRY(bn_backward_fed_from_above(m, v, b2, m->G(cur), t_c2, m->T(0), s));
+      else FDG_TRY(bn_backward(m, v, b2, m->G(cur), true, t_y, t_c2, nullptr, nullptr, m->T(0), s));
       FDG_TRY(mconv_wgrad(m, c2, t_a1, m->T(0), s));
       FDG_TRY(dgrad_relu_bn_backward(m, v, c2, m->T(0), v.Wt(c2), nullptr, b1, t_a1, t_c1, m->T(1), nullptr, nullptr, m->T(0), s));
       FDG_TRY(mconv_wgrad(m, c1, in_b, m->T(0), s));
@@ -829,8 +853,25 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
           FDG_TRY(mconv_dgrad(m, c1, m->T(0), v.Wt(c1), m->TP(), nullptr, m->G(nxt), m->GB(nxt), s));
         }
       } else if (need_dx) {
-        // identity shortcut: the masked incoming gradient joins the branch gradient
-        FDG_TRY(mconv_dgrad(m, c1, m->T(0), v.Wt(c1), m->G(cur), t_y, m->G(nxt), m->GB(nxt), s));
+        // identity shortcut: the masked incoming gradient joins the branch gradient.  Where the narrow kernel runs
+        // and the layer below ends in batch norm + ReLU, its output stage also does the first half of that layer's
+        // backward: the ReLU gate and the two sums of the batch norm.
+        const LayerPlan* below = li > 0 ? &p.L[li - 1] : nullptr;
+        const bool below_ok = below && (below->kind == FDG_BASIC_POSTACT || below->kind == FDG_STEM_CONV_BN_RELU);
+        const BnInfo* bb = below_ok ? &p.bns[below->kind == FDG_BASIC_POSTACT ? below->bn[1] : below->bn[0]] : nullptr;
+        if (!no_feed && bb && bb->C == c1.sh.Cip && conv_dgrad_feeds_next(c1.sh)) {
+          const bf16_t* bnx = v.act(below->kind == FDG_BASIC_POSTACT ? below->act[2] : below->act[0]);
+          FDG_TRY(side_wait_readers(m, m->GB(nxt), s));
+          const double bytes = 2 * conv_out_elems(c1.sh) + 2 * conv_w_elems(c1.sh) + conv_in_elems(c1.sh) * (4 + 2 + 2 + 2 + 4 + 2);
+          ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c1.sh), bytes, s);
+          const hipError_t e = conv_dgrad_feeding_next(c1.sh, m->T(0), v.Wt(c1), m->G(cur), t_y, in_b, bnx,
+                                                       m->bsums() + bb->stat_off, m->G(nxt), m->GB(nxt), s);
+          ps.label(c1.sh);
+          FDG_TRY(e);
+          fed = true;
+        } else {
+          FDG_TRY(mconv_dgrad(m, c1, m->T(0), v.Wt(c1), m->G(cur), t_y, m->G(nxt), m->GB(nxt), s));
+        }
       }
     } else {  // pre-activation block: y = conv2(o2) + shortcut
       const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]];

@@ -169,6 +169,11 @@ GATED_CASES = [  # data gradients the wide kernels run: output (= layer input) c
     (5, 4, 4, 128, 192, 1, 1),
     (2, 8, 8, 160, 160, 3, 1),      # contraction over 160 channels: a partly filled last 64-channel chunk
     (2, 8, 8, 160, 136, 3, 2),      # the same with parity classes (136 = 2 chunks + 8 channels)
+    # narrow layers: the gate and the sums in the output stage of the narrow kernel
+    (3, 7, 5, 16, 16, 3, 1),
+    (16, 32, 32, 16, 16, 3, 1),
+    (4, 16, 16, 32, 32, 3, 1),
+    (3, 8, 8, 64, 64, 3, 1),
 ]
 
 
@@ -230,15 +235,17 @@ def test_gated_data_gradient_feeds_the_batch_norm_backward(case):
     assert rel(dx16.to(t.float32).cpu().numpy(), dref) <= B16_TOL
 
 
-def test_gated_data_gradient_refuses_narrow_layers():
+def test_gated_data_gradient_refuses_layers_without_such_a_kernel():
+    """Neither the wide kernels nor the narrow one take a 24 -> 40 layer or a stride-2 16 -> 32 layer."""
     from paper_1906_09108_amd import kernels as K
     t = _torch()
-    assert not K.fdgk_conv_dgrad_gates(2, 8, 8, 16, 16, 3, 1)
-    z = t.zeros(2 * 8 * 8 * 16, dtype=t.bfloat16, device="cuda")
-    w = t.zeros(16 * 9 * 16, dtype=t.bfloat16, device="cuda")
-    st = t.zeros(32, dtype=t.float32, device="cuda")
+    assert not K.fdgk_conv_dgrad_gates(2, 8, 8, 24, 40, 3, 1)
+    assert not K.fdgk_conv_dgrad_gates(2, 8, 8, 16, 32, 3, 2)
+    z = t.zeros(2 * 8 * 8 * 40, dtype=t.bfloat16, device="cuda")
+    w = t.zeros(24 * 9 * 40, dtype=t.bfloat16, device="cuda")
+    st = t.zeros(48, dtype=t.float32, device="cuda")
     with pytest.raises(RuntimeError):
-        K.fdgk_conv_dgrad_gated(z, w, None, z, z, st, None, z, 2, 8, 8, 16, 16, 3, 1)
+        K.fdgk_conv_dgrad_gated(z, w, None, z, z, st, None, z, 2, 8, 8, 24, 40, 3, 1)
 
 
 @pytest.mark.parametrize("case", CONV_CASES)
