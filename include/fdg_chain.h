@@ -71,6 +71,11 @@ fdg_status fdg_chain_state(const fdg_chain* c, int64_t* iteration, int32_t* fwd_
  * and the mailbox memory stay with the caller.                                                     */
 void fdg_chain_destroy(fdg_chain* c);
 
+/* Learning rate of the paper's training runs (Section V-A) for a 0-based epoch of the 300: 0.1, divided by 10 at
+ * epochs 150, 225 and 275; with warmup_epochs > 0 (the paper: 3, for ResNet-110, ResNet-1202 and K = 3, 4) the
+ * first warmup_epochs epochs run at 0.01.  Host arithmetic only; negative arguments count as 0.                */
+float fdg_lr_schedule(int32_t epoch, int32_t warmup_epochs);
+
 #ifdef __cplusplus
 }
 #endif

@@ -43,7 +43,7 @@ class fdg_module_desc(ctypes.Structure):
 
 _lib: Optional[ctypes.CDLL] = None
 
-EXPORTS = ["fdg_module_workspace_bytes", "fdg_module_create", "fdg_module_workspace_bytes_ex", "fdg_module_create_ex", "fdg_forward", "fdg_backward_delayed", "fdg_update",
+EXPORTS = ["fdg_module_workspace_bytes", "fdg_module_create", "fdg_module_workspace_bytes_ex", "fdg_module_create_ex", "fdg_lr_schedule", "fdg_forward", "fdg_backward_delayed", "fdg_update",
            "fdg_destroy", "fdg_param_count", "fdg_set_params", "fdg_get_params", "fdg_get_grads", "fdg_get_momentum",
            "fdg_bn_stat_count", "fdg_get_bn_running", "fdg_output_shape", "fdg_queue_state", "fdg_status_string",
            "fdg_profile_enable", "fdg_profile_read", "fdg_input_shape", "fdg_module_traits",
@@ -63,6 +63,7 @@ def load() -> ctypes.CDLL:
     dp = ctypes.POINTER(fdg_module_desc)
     lib.fdg_module_workspace_bytes.argtypes, lib.fdg_module_workspace_bytes.restype = [dp], sz
     lib.fdg_module_create.argtypes, lib.fdg_module_create.restype = [dp, vp, sz, vp, ctypes.POINTER(vp)], i32
+    lib.fdg_lr_schedule.argtypes, lib.fdg_lr_schedule.restype = [i32, i32], ctypes.c_float
     lib.fdg_module_workspace_bytes_ex.argtypes, lib.fdg_module_workspace_bytes_ex.restype = [dp, i32], sz
     lib.fdg_module_create_ex.argtypes, lib.fdg_module_create_ex.restype = [dp, i32, vp, sz, vp, ctypes.POINTER(vp)], i32
     lib.fdg_forward.argtypes, lib.fdg_forward.restype = [vp, vp, vp, vp, vp], i32
@@ -137,6 +138,10 @@ def fdg_module_create(spec, workspace, stream=None) -> int:
 
 
 FDG_SAVE_ACTIVATIONS, FDG_SAVE_INPUT_AND_REPLAY = 0, 1
+
+
+def fdg_lr_schedule(epoch: int, warmup_epochs: int = 0) -> float:
+    return float(load().fdg_lr_schedule(int(epoch), int(warmup_epochs)))
 
 
 def fdg_module_workspace_bytes_ex(spec, save_mode: int) -> int:

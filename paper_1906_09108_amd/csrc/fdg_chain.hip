@@ -211,3 +211,12 @@ extern "C" void fdg_chain_destroy(fdg_chain* c) {
   (void)hipGetLastError();
   delete c;
 }
+
+extern "C" float fdg_lr_schedule(int32_t epoch, int32_t warmup_epochs) {
+  if (epoch < 0) epoch = 0;
+  if (epoch < warmup_epochs) return 0.01f;
+  if (epoch < 150) return 0.1f;
+  if (epoch < 225) return 0.01f;
+  if (epoch < 275) return 0.001f;
+  return 0.0001f;
+}

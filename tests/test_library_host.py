@@ -22,7 +22,7 @@ def _declared(header, prefix):
 def test_library_exports_every_declared_symbol():
     from paper_1906_09108_amd import kernels
     lib = binding.load()
-    names = sorted(set(_declared("fdg.h", "fdg_") + _declared("fdg_chain.h", "fdg_chain_")))
+    names = sorted(set(_declared("fdg.h", "fdg_") + _declared("fdg_chain.h", "fdg_")))
     assert set(names) == set(binding.EXPORTS)
     knames = _declared("fdg_kernels.h", "fdgk_")
     assert set(knames) == set(kernels.KERNEL_EXPORTS)
@@ -106,3 +106,16 @@ def test_chain_rejects_bad_arguments_without_a_gpu():
     assert lib.fdg_chain_step(None, None, None, 0.1, None, None, None) == binding.FDG_ERR_INVALID_ARG
     assert lib.fdg_chain_state(None, None, None, None) == binding.FDG_ERR_INVALID_ARG
     lib.fdg_chain_destroy(None)
+
+
+def test_learning_rate_schedule_of_section_5a():
+    """Section V-A: lr 0.1, divided by 10 at epochs 150, 225 and 275 of 300; 0.01 for the first 3 epochs where the
+    paper warms up.  The expected values are the paper's, typed in."""
+    f = binding.fdg_lr_schedule
+    for epoch, lr in ((0, 0.1), (1, 0.1), (149, 0.1), (150, 0.01), (224, 0.01), (225, 0.001), (274, 0.001), (275, 0.0001),
+                      (299, 0.0001)):
+        assert f(epoch) == pytest.approx(lr, rel=1e-6), epoch
+    for epoch, lr in ((0, 0.01), (2, 0.01), (3, 0.1), (149, 0.1), (150, 0.01), (299, 0.0001)):
+        assert f(epoch, 3) == pytest.approx(lr, rel=1e-6), epoch
+    assert f(-5) == pytest.approx(0.1, rel=1e-6)
+
