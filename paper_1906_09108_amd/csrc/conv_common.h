@@ -119,7 +119,7 @@ __device__ __forceinline__ void store_tile(const GatherConvArgs& a, const f32x4 
     __syncthreads();
     for (int t = threadIdx.x; t < 2 * BN; t += blockDim.x) {
       const int c = c_tile + (t % BN);
-      if (c < a.Co) atomicAdd(a.stats + (t / BN) * a.Co + c, red[t]);
+      if (c < a.Co) atomicAdd(a.stats + (size_t)(blockIdx.x % kStatReplicas) * a.stats_rep_stride + (t / BN) * a.Co + c, red[t]);
     }
   }
 }
@@ -301,7 +301,7 @@ __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x
 #pragma unroll
           for (int w = 0; w < PARKW; ++w) sum += park[(size_t)((w * PERIOD + k) * 64 + l) * 8 + which * 4 + e];
       }
-      atomicAdd(a.stats + which * a.Co + c, sum);
+      atomicAdd(a.stats + (size_t)(blockIdx.x % kStatReplicas) * a.stats_rep_stride + which * a.Co + c, sum);
     }
   }
 }

@@ -361,8 +361,9 @@ hipError_t launch_conv_wgrad(const WgradArgs& a, hipStream_t s) {
 // geometry of the three passes of one convolution
 // ------------------------------------------------------------------------------------------------
 hipError_t conv_forward(const ConvShape& c, const bf16_t* x, const bf16_t* w, const float* addend, float* out_f32,
-                        bf16_t* out_b16, float* stats, hipStream_t s) {
+                        bf16_t* out_b16, float* stats, hipStream_t s, int stats_rep_stride) {
   GatherConvArgs a{};
+  a.stats_rep_stride = stats_rep_stride;
   a.in = x; a.w = w; a.addend = addend; a.addmask = nullptr; a.out_f32 = out_f32; a.out_b16 = out_b16; a.stats = stats;
   a.N = c.N; a.Hi = c.Hi; a.Wi = c.Wi; a.Ci = c.Cip;
   a.OH = c.Ho(); a.OW = c.Wo(); a.in_stride = c.stride;
@@ -380,7 +381,7 @@ hipError_t conv_forward(const ConvShape& c, const bf16_t* x, const bf16_t* w, co
 
 static hipError_t conv_dgrad_impl(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                                   const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, float* gsums, float* out_f32,
-                                  bf16_t* out_b16, hipStream_t s, bool stats_f32 = false);
+                                  bf16_t* out_b16, hipStream_t s, bool stats_f32 = false, int rep_stride = 0);
 
 hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                       const bf16_t* addmask, float* out_f32, bf16_t* out_b16, hipStream_t s) {
@@ -400,9 +401,9 @@ bool conv_dgrad_feeds_next(const ConvShape& c) {
 
 hipError_t conv_dgrad_feeding_next(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                                    const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, float* gsums, float* out_f32,
-                                   bf16_t* out_b16, hipStream_t s) {
+                                   bf16_t* out_b16, hipStream_t s, int gsums_rep_stride) {
   if (!gate || !bnx || !gsums || !out_f32 || !conv_dgrad_feeds_next(c)) return hipErrorInvalidValue;
-  return conv_dgrad_impl(c, dy, wt, addend, addmask, gate, bnx, gsums, out_f32, out_b16, s, /*stats_f32=*/true);
+  return conv_dgrad_impl(c, dy, wt, addend, addmask, gate, bnx, gsums, out_f32, out_b16, s, /*stats_f32=*/true, gsums_rep_stride);
 }
 
 // The gate and the sums are taken where the wide kernels or the narrow kernel run the whole data gradient.
@@ -414,15 +415,17 @@ bool conv_dgrad_gates(const ConvShape& c) {
 }
 
 hipError_t conv_dgrad_gated(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend, const bf16_t* gate,
-                            const bf16_t* bnx, float* gsums, float* out_f32, bf16_t* out_b16, hipStream_t s) {
+                            const bf16_t* bnx, float* gsums, float* out_f32, bf16_t* out_b16, hipStream_t s,
+                            int gsums_rep_stride) {
   if (!gate || !bnx || !gsums || !conv_dgrad_gates(c)) return hipErrorInvalidValue;
-  return conv_dgrad_impl(c, dy, wt, addend, nullptr, gate, bnx, gsums, out_f32, out_b16, s);
+  return conv_dgrad_impl(c, dy, wt, addend, nullptr, gate, bnx, gsums, out_f32, out_b16, s, false, gsums_rep_stride);
 }
 
 static hipError_t conv_dgrad_impl(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                                   const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, float* gsums, float* out_f32,
-                                  bf16_t* out_b16, hipStream_t s, bool stats_f32) {
+                                  bf16_t* out_b16, hipStream_t s, bool stats_f32, int rep_stride) {
   GatherConvArgs a{};
+  a.stats_rep_stride = rep_stride;
   a.in = dy; a.w = wt; a.addend = addend; a.addmask = addmask; a.out_f32 = out_f32; a.out_b16 = out_b16;
   a.gate = gate; a.bnx = bnx; a.stats = gsums; a.stats_f32 = stats_f32 ? 1 : 0;
   a.N = c.N; a.Hi = c.Ho(); a.Wi = c.Wo(); a.Ci = c.Co;

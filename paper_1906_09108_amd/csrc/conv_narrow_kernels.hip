@@ -26,11 +26,140 @@ __device__ __forceinline__ void narrow_dma16(const void* gsrc, void* lds_wave_ba
                                    (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
 }
 
+// n / d for n < 2^30 and d <= 1024 with one 64-bit multiply: magic = ceil(2^40 / d) (exact: the error term
+// n * (magic * d - 2^40) stays below 2^40)
+__device__ __forceinline__ int narrow_div(int n, unsigned long long magic) {
+  return (int)(((unsigned long long)(unsigned)n * magic) >> 40);
+}
+struct NarrowLaunch {
+  int units;                        // 16-byte units of patch in LDS (a multiple of 256)
+  unsigned long long magic_w, magic_h;
+};
+
+// Output stage: what store_tile does for a same-grid unit-stride output (so the flat pixel index is the output
+// index and no coordinates are needed), with every optional operand of all J pixel blocks requested before the
+// first is used -- one memory round trip instead of one per operand and block -- and the per-channel sums of the
+// four waves added through LDS without atomics (one barrier).
+template <int J, int NB, int WN, int CO>
+__device__ __forceinline__ void narrow_store(const GatherConvArgs& a, const f32x4 (&acc)[NB][J], int m_base, int wave, int lane,
+                                             int Mtot) {
+  constexpr int WM = 4 / WN;
+  const int wn = wave / WM;
+  const int c0 = wn * NB * 16 + 4 * (lane >> 4);   // this lane's first channel of block 0
+  size_t o[J];
+  bool okp[J];
+#pragma unroll
+  for (int j = 0; j < J; ++j) {
+    const int m = m_base + j * 16 + (lane & 15);
+    okp[j] = m < Mtot;
+    o[j] = (size_t)(okp[j] ? m : 0) * CO + c0;
+  }
+  float4 ad[J][NB];
+  uint2 mk[J][NB], gt[J][NB], bx[J][NB];
+  const bool want_bx = a.bnx && a.stats;
+  if (a.addend) {
+#pragma unroll
+    for (int j = 0; j < J; ++j)
+#pragma unroll
+      for (int i = 0; i < NB; ++i) ad[j][i] = *reinterpret_cast<const float4*>(a.addend + o[j] + i * 16);
+  }
+  if (a.addend && a.addmask) {
+#pragma unroll
+    for (int j = 0; j < J; ++j)
+#pragma unroll
+      for (int i = 0; i < NB; ++i) mk[j][i] = *reinterpret_cast<const uint2*>(a.addmask + o[j] + i * 16);
+  }
+  if (a.gate) {
+#pragma unroll
+    for (int j = 0; j < J; ++j)
+#pragma unroll
+      for (int i = 0; i < NB; ++i) gt[j][i] = *reinterpret_cast<const uint2*>(a.gate + o[j] + i * 16);
+  }
+  if (want_bx) {
+#pragma unroll
+    for (int j = 0; j < J; ++j)
+#pragma unroll
+      for (int i = 0; i < NB; ++i) bx[j][i] = *reinterpret_cast<const uint2*>(a.bnx + o[j] + i * 16);
+  }
+  float s1[NB][4], s2[NB][4];
+#pragma unroll
+  for (int i = 0; i < NB; ++i)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) s1[i][v] = s2[i][v] = 0.f;
+#pragma unroll
+  for (int j = 0; j < J; ++j)
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      f32x4 v = acc[i][j];
+      if (a.addend) {
+        float4 d = ad[j][i];
+        if (a.addmask) {
+          if (!(bf16_lo(mk[j][i].x) > 0.f)) d.x = 0.f;
+          if (!(bf16_hi(mk[j][i].x) > 0.f)) d.y = 0.f;
+          if (!(bf16_lo(mk[j][i].y) > 0.f)) d.z = 0.f;
+          if (!(bf16_hi(mk[j][i].y) > 0.f)) d.w = 0.f;
+        }
+        v[0] += d.x; v[1] += d.y; v[2] += d.z; v[3] += d.w;
+      }
+      if (a.gate) {
+        if (!(bf16_lo(gt[j][i].x) > 0.f)) v[0] = 0.f;
+        if (!(bf16_hi(gt[j][i].x) > 0.f)) v[1] = 0.f;
+        if (!(bf16_lo(gt[j][i].y) > 0.f)) v[2] = 0.f;
+        if (!(bf16_hi(gt[j][i].y) > 0.f)) v[3] = 0.f;
+      }
+      const uint2 packed = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+      if (okp[j]) {
+        if (a.out_f32) *reinterpret_cast<float4*>(a.out_f32 + o[j] + i * 16) = make_float4(v[0], v[1], v[2], v[3]);
+        if (a.out_b16) *reinterpret_cast<uint2*>(a.out_b16 + o[j] + i * 16) = packed;
+        if (a.stats) {
+          const bool f = a.stats_f32 != 0;
+          const float r0 = f ? v[0] : bf16_lo(packed.x), r1 = f ? v[1] : bf16_hi(packed.x);
+          const float r2 = f ? v[2] : bf16_lo(packed.y), r3 = f ? v[3] : bf16_hi(packed.y);
+          s1[i][0] += r0; s1[i][1] += r1; s1[i][2] += r2; s1[i][3] += r3;
+          if (want_bx) {
+            s2[i][0] += r0 * bf16_lo(bx[j][i].x); s2[i][1] += r1 * bf16_hi(bx[j][i].x);
+            s2[i][2] += r2 * bf16_lo(bx[j][i].y); s2[i][3] += r3 * bf16_hi(bx[j][i].y);
+          } else {
+            s2[i][0] += r0 * r0; s2[i][1] += r1 * r1; s2[i][2] += r2 * r2; s2[i][3] += r3 * r3;
+          }
+        }
+      }
+    }
+  if (a.stats) {
+    // over the 16 lanes that hold the same 4 channels, then one slot per wave in LDS, then over the waves
+    __shared__ float red[4][2][NB * 16];
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        float x1 = s1[i][v], x2 = s2[i][v];
+#pragma unroll
+        for (int off = 8; off > 0; off >>= 1) {
+          x1 += __shfl_xor(x1, off, 16);
+          x2 += __shfl_xor(x2, off, 16);
+        }
+        if ((lane & 15) == 0) {
+          red[wave][0][i * 16 + 4 * (lane >> 4) + v] = x1;
+          red[wave][1][i * 16 + 4 * (lane >> 4) + v] = x2;
+        }
+      }
+    __syncthreads();
+    for (int t = threadIdx.x; t < 2 * CO; t += 256) {
+      const int which = t / CO, c = t % CO;
+      const int owner = c / (NB * 16), cl = c % (NB * 16);   // the WM waves with wn == owner hold channel c
+      float sum = 0.f;
+#pragma unroll
+      for (int w = 0; w < WM; ++w) sum += red[owner * WM + w][which][cl];
+      atomicAdd(a.stats + (size_t)(blockIdx.x % kStatReplicas) * a.stats_rep_stride + which * CO + c, sum);
+    }
+  }
+}
+
 // CI input channels; a wave owns J blocks of 16 pixels and NB blocks of 16 output channels; WN waves side by side
 // over the output channels (Co = 16 * NB * WN), 4 / WN over the pixels.  LDS: `units` 16-byte units of patch
 // (a multiple of 256: whole load rounds of the workgroup) followed by 128 bytes of zeros.
 template <int CI, int NB, int WN, int J>
-__global__ __launch_bounds__(256) void conv_narrow_kernel(GatherConvArgs a, int units) {
+__global__ __launch_bounds__(256) void conv_narrow_kernel(GatherConvArgs a, NarrowLaunch L) {
   constexpr int WM = 4 / WN, TP = 16 * J * WM, CO = 16 * NB * WN;
   constexpr int U = CI / 8, ROWB = CI * 2;          // 16-byte units and bytes of one pixel
   constexpr int S = (9 * CI + 31) / 32;             // 32-wide steps of the contraction (taps x channels)
@@ -43,7 +172,7 @@ __global__ __launch_bounds__(256) void conv_narrow_kernel(GatherConvArgs a, int 
   const int W = a.Wi, H = a.Hi;
   const int Mtot = a.N * H * W;
   const int m0 = blockIdx.x * TP;
-  const int rows = TP + 2 * W + 2;                   // patch row r holds pixel m0 - W - 1 + r
+  const int units = L.units;                         // patch row r holds pixel m0 - W - 1 + r
 
   // ---- the patch: one burst of loads, lane i of a round lands at unit position base + i ----
   for (int base = wave * 64; base < units; base += 256) {
@@ -85,7 +214,8 @@ __global__ __launch_bounds__(256) void conv_narrow_kernel(GatherConvArgs a, int 
       const int pl = (wm * J + j) * 16 + (lane & 15);
       const int m = m0 + pl;
       const bool inside = m < Mtot;
-      const int ow = m % W, oh = (m / W) % H;
+      const int row = narrow_div(m, L.magic_w), ow = m - row * W;   // image row over the whole batch, column
+      const int oh = row - narrow_div(row, L.magic_h) * H;
 #pragma unroll
       for (int s = 0; s < SA; ++s) {
         // which tap and which unit of the pixel this lane's 8 k values are
@@ -123,8 +253,8 @@ __global__ __launch_bounds__(256) void conv_narrow_kernel(GatherConvArgs a, int 
       for (int nb = 0; nb < NB; ++nb) acc[nb][j] = mfma16(wf[s][nb], b, acc[nb][j]);
     }
 
-  (void)rows;
-  store_tile<J, NB, CO>(a, acc, m0 + wm * J * 16, 0, wn * NB * 16, lane);
+  (void)wn;
+  narrow_store<J, NB, WN, CO>(a, acc, m0 + wm * J * 16, wave, lane, Mtot);
 }
 
 template <int CI, int NB, int WN, int J>
@@ -144,7 +274,11 @@ hipError_t run_narrow(const GatherConvArgs& a, hipStream_t s) {
   static char name[64];
   if (!name[0]) snprintf(name, sizeof(name), "conv_narrow_kernel<%d, %d, %d, %d>", CI, NB, WN, J);
   note_kernel(name);
-  hipLaunchKernelGGL((conv_narrow_kernel<CI, NB, WN, J>), dim3((Mtot + TP - 1) / TP), dim3(256), lds, s, a, units);
+  NarrowLaunch L;
+  L.units = units;
+  L.magic_w = ((1ull << 40) + a.Wi - 1) / a.Wi;
+  L.magic_h = ((1ull << 40) + a.Hi - 1) / a.Hi;
+  hipLaunchKernelGGL((conv_narrow_kernel<CI, NB, WN, J>), dim3((Mtot + TP - 1) / TP), dim3(256), lds, s, a, L);
   return hipGetLastError();
 }
 
@@ -380,7 +514,7 @@ bool conv_narrow_applies(const GatherConvArgs& a) {
   if (a.Ci != 16 && a.Ci != 32 && a.Ci != 64) return false;
   if (a.Co != a.Ci || a.w_rows != a.Co || a.Kw != 9 * a.Ci) return false;
   if (a.ntaps != 9 || a.in_stride != 1 || a.out_stride != 1 || a.ooh != 0 || a.oow != 0 || a.nclass > 1) return false;
-  if (a.OH != a.Hi || a.OW != a.Wi || a.OHf != a.OH || a.OWf != a.OW || a.Wi < 1) return false;
+  if (a.OH != a.Hi || a.OW != a.Wi || a.OHf != a.OH || a.OWf != a.OW || a.Wi < 1 || a.Wi > 1024 || a.Hi > 1024) return false;
   if ((long long)a.N * a.Hi * a.Wi >= (1ll << 30)) return false;
   for (int i = 0; i < 9; ++i) {
     const int dh = (a.tap[i] & 0xff) - 8, dw = ((a.tap[i] >> 8) & 0xff) - 8;

@@ -18,6 +18,12 @@ __host__ __device__ static inline int pack_tap(int dh, int dw, int kofs) { retur
 // Rows m enumerate an output grid [N, OH, OW]; the output pixel of row (n, oh, ow) is
 // (n, oh*out_stride + ooh, ow*out_stride + oow) in a tensor [N, OHf, OWf, Co].  Forward convolution,
 // stride-1 data gradient and each parity class of a stride-2 data gradient are all of this form.
+// Per-channel sums are added with one atomic request per workgroup; hundreds of workgroups onto one cache line
+// serialise at the memory side (6 - 11 us per launch for the narrow layers).  A sums array may therefore exist in
+// kStatReplicas copies, rep_stride floats apart: workgroup b adds into copy b % kStatReplicas and whoever reads the
+// sums adds the copies (in a fixed order).  rep_stride = 0: a single copy.
+constexpr int kStatReplicas = 8;
+
 struct GatherConvArgs {
   const bf16_t* in;      // [N, Hi, Wi, Ci] bf16, Ci % 8 == 0
   const bf16_t* w;       // [w_rows, Kw] bf16, k contiguous
@@ -30,6 +36,7 @@ struct GatherConvArgs {
   const bf16_t* gate;    // optional (output indexing): the output is kept where gate > 0 and is zero elsewhere
   const bf16_t* bnx;     // optional (output indexing), with stats: stats[Co + c] += sum of output * bnx instead of
                          // the squares -- with stats[c] the two sums the batch-norm backward needs
+  int stats_rep_stride;  // floats between the copies of stats (0: one copy)
   int stats_f32;         // with bnx, narrow / generic output stage: the sums are of the fp32 values, not of the bf16 output
   int N, Hi, Wi, Ci;
   int OH, OW, in_stride;
@@ -85,7 +92,7 @@ struct ConvShape {
 // stats (optional, [2*Co], pre-zeroed): += per-channel sum and sum of squares of the bf16-rounded result,
 // i.e. the batch-norm statistics of the tensor just produced
 hipError_t conv_forward(const ConvShape& c, const bf16_t* x, const bf16_t* w, const float* addend, float* out_f32,
-                        bf16_t* out_b16, float* stats, hipStream_t s);
+                        bf16_t* out_b16, float* stats, hipStream_t s, int stats_rep_stride = 0);
 // dx[N,Hi,Wi,Cip] = conv^T(dy[N,Ho,Wo,Co], wt[Cip][T][Co]) (+ addend, optionally only where addmask > 0)
 hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                       const bf16_t* addmask, float* out_f32, bf16_t* out_b16, hipStream_t s);
@@ -97,10 +104,11 @@ hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, co
 bool conv_dgrad_feeds_next(const ConvShape& c);
 hipError_t conv_dgrad_feeding_next(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                                    const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, float* gsums, float* out_f32,
-                                   bf16_t* out_b16, hipStream_t s);
+                                   bf16_t* out_b16, hipStream_t s, int gsums_rep_stride = 0);
 bool conv_dgrad_gates(const ConvShape& c);
 hipError_t conv_dgrad_gated(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend, const bf16_t* gate,
-                            const bf16_t* bnx, float* gsums, float* out_f32, bf16_t* out_b16, hipStream_t s);
+                            const bf16_t* bnx, float* gsums, float* out_f32, bf16_t* out_b16, hipStream_t s,
+                            int gsums_rep_stride = 0);
 // dw[Co][T][Ci] (+)= sum over pixels of dy * x.  overwrite = false: accumulated into dw (fp32 atomics where the
 // pixel dimension is split), dw zeroed by the caller;  overwrite = true: dw is written, whatever it held.
 // scratch (optional): device memory for the partial sums of the pixel splits; without it they are added
@@ -132,6 +140,7 @@ struct BnApplyArgs {
   int M, C;
   float eps, momentum;
   int relu;
+  int rep_stride;        // floats between the copies of sums and of sums2 (0: one copy)
 };
 hipError_t launch_bn_apply(const BnApplyArgs& a, hipStream_t s);
 
@@ -153,6 +162,8 @@ struct BnBwdArgs {
   float eps;
   int dy_gated;          // apply only: dy is already zero where the gate is closed (mask is not read)
   int raw_sums;          // apply only: bsums holds sum g and sum g*x (not g*xhat), as a gated data gradient leaves them
+  int rep_stride;        // floats between the copies of sums (0: one copy)
+  int brep_stride;       // apply only: floats between the copies of bsums (0: one copy); the reduce pass adds into copy 0
 };
 hipError_t launch_bn_bwd_reduce(const BnBwdArgs& a, hipStream_t s);
 hipError_t launch_bn_bwd_apply(const BnBwdArgs& a, hipStream_t s);

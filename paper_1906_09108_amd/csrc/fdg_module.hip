@@ -61,6 +61,8 @@ struct Plan {
   size_t P = 0;                // internal parameter arena (elements, multiple of 4)
   size_t small_off = 0, small_count = 0;
   size_t stat_floats = 0;      // 2 * sum of BN channels
+  int stat_rep = 0;            // floats between the copies of a sums array: stat_floats where the narrow kernels run
+                               // (hundreds of small workgroups add into the sums), else 0 = a single copy
   size_t warena_elems = 0;     // bf16 elements of one slot's weight arena
   size_t emit_blocks = 0;
   size_t maxE = 0;             // largest activation tensor in elements
@@ -239,13 +241,16 @@ bool build_plan(const fdg_module_desc* desc, int save_mode, Plan& p, fdg_status*
   p.P = p.small_off + p.small_count;
   if (p.P >= (1ull << 31) || p.warena_elems >= (1ull << 32) || p.maxE >= (1ull << 31)) { *why = FDG_ERR_UNSUPPORTED; return false; }
   for (const ConvInfo& ci : p.convs) p.emit_blocks += emit_blocks_for(ci.sh.Co, ci.sh.Cip, ci.sh.T);
+  for (const ConvInfo& ci : p.convs)
+    if (conv_dgrad_feeds_next(ci.sh)) p.stat_rep = (int)p.stat_floats;
+  const size_t stat_copies = p.stat_rep ? kStatReplicas : 1;
   // workspace layout
   size_t o = 0;
   auto take = [&](size_t bytes) { const size_t at = o; o += align_up(bytes, kAlign); return at; };
   p.o_params = take(p.P * 4);
   p.o_mom = take(p.P * 4);
   p.o_grads = take(p.P * 4);
-  p.o_bsums = take(p.stat_floats * 4);
+  p.o_bsums = take(p.stat_floats * 4 * stat_copies);   // the copies are stat_floats apart
   p.o_running = take(p.stat_floats * 4);
   p.o_table = take(p.convs.size() * sizeof(WeightEmitEntry));
   {  // one slot; the intermediates follow the snapshots inside it, or form a region of their own (replay)
@@ -259,7 +264,7 @@ bool build_plan(const fdg_module_desc* desc, int save_mode, Plan& p, fdg_status*
     p.s_small = stake(p.small_count * 4);
     if (p.is_top) p.s_labels = stake((size_t)N * 4);
     if (p.replay) p.s_xcopy = stake((size_t)N * desc->c_in * desc->h_in * desc->w_in * 4);
-    p.s_sums = itake(p.stat_floats * 4);
+    p.s_sums = itake(p.stat_floats * 4 * stat_copies);
     p.s_xin = itake((size_t)N * desc->h_in * desc->w_in * p.Cp_in * 2);
     p.s_acts = itake(act_bytes);
     if (p.is_top) {
@@ -429,7 +434,7 @@ hipError_t mconv_forward(const fdg_module* m, const ConvInfo& c, const bf16_t* x
   const double bytes = 2 * conv_in_elems(c.sh) + 2 * conv_w_elems(c.sh) +
                        conv_out_elems(c.sh) * ((addend ? 4 : 0) + (out_f32 ? 4 : 0) + (out_b16 ? 2 : 0));
   ProfScope ps(m, PC_CONV_FWD, conv_flops(c.sh), bytes, s);
-  const hipError_t e = conv_forward(c.sh, x, w, addend, out_f32, out_b16, stats, s);
+  const hipError_t e = conv_forward(c.sh, x, w, addend, out_f32, out_b16, stats, s, m->p.stat_rep);
   ps.label(c.sh);
   return e;
 }
@@ -526,6 +531,7 @@ hipError_t bn_apply(const fdg_module* m, const SlotView& v, const BnInfo& b, con
   a.out_f32 = out_f32; a.out_b16 = out_b16;
   if (!replayed) { a.run_mean = m->running() + b.stat_off; a.run_var = m->running() + b.stat_off + b.C; }
   a.M = b.M; a.C = b.C; a.eps = m->p.d.bn_eps; a.momentum = m->p.d.bn_momentum; a.relu = 1;
+  a.rep_stride = m->p.stat_rep;
   ProfScope ps(m, PC_BN_APPLY, 0, (double)b.M * b.C * (2 + (res ? 4 : 0) + (b2 ? 2 : 0) + (out_f32 ? 4 : 0) + (out_b16 ? 2 : 0)), s);
   return launch_bn_apply(a, s);
 }
@@ -541,6 +547,7 @@ hipError_t bn_backward(const fdg_module* m, const SlotView& v, const BnInfo& b, 
   a.addend = addend; a.out_f32 = out_f32; a.out_b16 = out_b16;
   a.dgamma = m->grads() + b.gamma_off; a.dbeta = m->grads() + b.beta_off;
   a.M = b.M; a.C = b.C; a.eps = m->p.d.bn_eps;
+  a.rep_stride = a.brep_stride = m->p.stat_rep;
   if (hipError_t e = side_wait_readers(m, out_b16, s); e != hipSuccess) return e;
   // the reduce pass reads dy, gate and x; the apply pass reads them again and writes dx
   const double rd = (dy_f32 ? 4 : 2) + 2 + 2;
@@ -563,6 +570,7 @@ hipError_t bn_backward_after_gated_dgrad(const fdg_module* m, const SlotView& v,
   a.addend = addend; a.out_f32 = out_f32; a.out_b16 = out_b16;
   a.dgamma = m->grads() + b.gamma_off; a.dbeta = m->grads() + b.beta_off;
   a.M = b.M; a.C = b.C; a.eps = m->p.d.bn_eps;
+  a.rep_stride = a.brep_stride = m->p.stat_rep;
   a.dy_gated = 1; a.raw_sums = 1;
   if (hipError_t e = side_wait_readers(m, out_b16, s); e != hipSuccess) return e;
   ProfScope ps(m, PC_BN_BWD, 0, (double)b.M * b.C * ((out_f32 || out_b16 ? 4 : 0) + (addend ? 4 : 0) + (out_f32 ? 4 : 0) +
@@ -581,6 +589,7 @@ hipError_t bn_backward_fed_from_above(const fdg_module* m, const SlotView& v, co
   a.out_b16 = out_b16;
   a.dgamma = m->grads() + b.gamma_off; a.dbeta = m->grads() + b.beta_off;
   a.M = b.M; a.C = b.C; a.eps = m->p.d.bn_eps;
+  a.rep_stride = a.brep_stride = m->p.stat_rep;
   a.dy_gated = 1; a.raw_sums = 1;
   if (hipError_t e = side_wait_readers(m, out_b16, s); e != hipSuccess) return e;
   ProfScope ps(m, PC_BN_BWD, 0, (double)b.M * b.C * (4 + 2 + 2), s);
@@ -599,7 +608,8 @@ hipError_t dgrad_relu_bn_backward(const fdg_module* m, const SlotView& v, const 
     {
       const double bytes = 2 * conv_out_elems(c.sh) + 2 * conv_w_elems(c.sh) + conv_in_elems(c.sh) * ((dgrad_addend ? 4 : 0) + 2 + 2 + 2);
       ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c.sh), bytes, s);
-      const hipError_t e = conv_dgrad_gated(c.sh, dy, wt, dgrad_addend, gate, x, m->bsums() + b.stat_off, nullptr, g, s);
+      const hipError_t e = conv_dgrad_gated(c.sh, dy, wt, dgrad_addend, gate, x, m->bsums() + b.stat_off, nullptr, g, s,
+                                            m->p.stat_rep);
       ps.label(c.sh);
       if (e != hipSuccess) return e;
     }
@@ -616,7 +626,7 @@ hipError_t dgrad_relu_bn_backward(const fdg_module* m, const SlotView& v, const 
 fdg_status forward_pass(fdg_module* m, const SlotView& v, const float* x_dev, float* y_dev, bool replayed, hipStream_t s) {
   const Plan& p = m->p;
   const int N = p.d.n;
-  if (p.stat_floats) FDG_TRY(launch_fill_zero(v.sums(p.bns[0]), align_up(p.stat_floats * 4, 16), s));
+  if (p.stat_floats) FDG_TRY(launch_fill_zero(v.sums(p.bns[0]), align_up(p.stat_floats * 4 * (p.stat_rep ? kStatReplicas : 1), 16), s));
   // module input: fp32 NCHW -> fp32 NHWC stream + bf16 NHWC copy (kept for the backward)
   int cur = 0;
   FDG_TRY(launch_nchw_to_nhwc(x_dev, (p.d.c_in % 8 == 0) ? m->S(cur) : nullptr, v.xin(), N, p.d.c_in, p.d.h_in * p.d.w_in,
@@ -865,7 +875,7 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
           const double bytes = 2 * conv_out_elems(c1.sh) + 2 * conv_w_elems(c1.sh) + conv_in_elems(c1.sh) * (4 + 2 + 2 + 2 + 4 + 2);
           ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c1.sh), bytes, s);
           const hipError_t e = conv_dgrad_feeding_next(c1.sh, m->T(0), v.Wt(c1), m->G(cur), t_y, in_b, bnx,
-                                                       m->bsums() + bb->stat_off, m->G(nxt), m->GB(nxt), s);
+                                                       m->bsums() + bb->stat_off, m->G(nxt), m->GB(nxt), s, p.stat_rep);
           ps.label(c1.sh);
           FDG_TRY(e);
           fed = true;

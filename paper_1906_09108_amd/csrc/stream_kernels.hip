@@ -24,6 +24,25 @@ __device__ __forceinline__ void load8_f32(const float* p, float (&f)[8]) {
   const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
   f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
 }
+// the same, adding the copies of a replicated sums array (rep = floats between copies, 0: one copy)
+__device__ __forceinline__ void load8_rep(const float* p, int rep, float (&v)[8]) {
+  load8_f32(p, v);
+  if (rep > 0) {
+#pragma unroll
+    for (int r = 1; r < kStatReplicas; ++r) {
+      float t[8];
+      load8_f32(p + (size_t)r * rep, t);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] += t[i];
+    }
+  }
+}
+__device__ __forceinline__ float load_rep(const float* p, int rep) {
+  float v = p[0];
+  if (rep > 0)
+    for (int r = 1; r < kStatReplicas; ++r) v += p[(size_t)r * rep];
+  return v;
+}
 __device__ __forceinline__ void store8_f32(float* p, const float (&f)[8]) {
   *reinterpret_cast<float4*>(p) = make_float4(f[0], f[1], f[2], f[3]);
   *reinterpret_cast<float4*>(p + 4) = make_float4(f[4], f[5], f[6], f[7]);
@@ -111,12 +130,12 @@ hipError_t launch_bn_stats(const bf16_t* x, float* sums, int M, int C, hipStream
 }
 
 // ---- BN apply: y = relu?( gamma*xhat + beta [+ res] [+ gamma2*xhat2 + beta2] ) ------------------------
-__device__ __forceinline__ void bn_running(const float* sums, float* run_mean, float* run_var, int C, int M, float mom) {
+__device__ __forceinline__ void bn_running(const float* sums, int rep, float* run_mean, float* run_var, int C, int M, float mom) {
   const float invM = 1.f / (float)M;
   const float unbias = M > 1 ? (float)M / (float)(M - 1) : 1.f;
   for (int c = threadIdx.x; c < C; c += blockDim.x) {
-    const float mean = sums[c] * invM;
-    const float var = fmaxf(sums[C + c] * invM - mean * mean, 0.f);
+    const float mean = load_rep(sums + c, rep) * invM;
+    const float var = fmaxf(load_rep(sums + C + c, rep) * invM - mean * mean, 0.f);
     run_mean[c] = (1.f - mom) * run_mean[c] + mom * mean;
     run_var[c] = (1.f - mom) * run_var[c] + mom * var * unbias;
   }
@@ -146,12 +165,54 @@ static ApplyShape apply_shape(int M, int C) {
   return r;
 }
 
+// The copies of NA replicated per-channel arrays added once per block instead of once per thread: thread
+// (cgl = tid % CGB, rl = tid / CGB) with rl < kStatReplicas loads copy rl of its channel group (8 floats per array),
+// the copies are added across the lanes of wave 0 (needs kStatReplicas * CGB <= 64, CGB a power of two) and parked
+// in LDS, where every thread of the block picks up the sums of its channel group.  All threads of the block call.
+template <int NA>
+__device__ __forceinline__ void fold_replicas(const float* const (&src)[NA], const int (&rep)[NA], int c0, bool cvalid, int CGB,
+                                              float (&out)[NA][8]) {
+  __shared__ float4 parked[8][NA][2];
+  const int cgl = threadIdx.x % CGB, rl = threadIdx.x / CGB;
+  if (rl < kStatReplicas) {
+    float v[NA][8];
+#pragma unroll
+    for (int a = 0; a < NA; ++a) {
+      if (cvalid && (rl == 0 || rep[a] > 0)) load8_f32(src[a] + c0 + (size_t)rl * rep[a], v[a]);
+      else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[a][i] = 0.f;
+      }
+    }
+    for (int off = CGB; off < kStatReplicas * CGB; off <<= 1) {
+#pragma unroll
+      for (int a = 0; a < NA; ++a)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[a][i] += __shfl_xor(v[a][i], off);
+    }
+    if (rl == 0) {
+#pragma unroll
+      for (int a = 0; a < NA; ++a) {
+        parked[cgl][a][0] = make_float4(v[a][0], v[a][1], v[a][2], v[a][3]);
+        parked[cgl][a][1] = make_float4(v[a][4], v[a][5], v[a][6], v[a][7]);
+      }
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int a = 0; a < NA; ++a) {
+    const float4 lo = parked[cgl][a][0], hi = parked[cgl][a][1];
+    out[a][0] = lo.x; out[a][1] = lo.y; out[a][2] = lo.z; out[a][3] = lo.w;
+    out[a][4] = hi.x; out[a][5] = hi.y; out[a][6] = hi.z; out[a][7] = hi.w;
+  }
+}
+
 // scale / shift of 8 channels from the accumulated sums
-__device__ __forceinline__ void bn_coeffs8(const float* sums, const float* gamma, const float* beta, int C, int c0, float invM,
+__device__ __forceinline__ void bn_coeffs8(const float* sums, int rep, const float* gamma, const float* beta, int C, int c0, float invM,
                                            float eps, float (&sc)[8], float (&sh)[8]) {
   float s1[8], s2[8], g[8], b[8];
-  load8_f32(sums + c0, s1);
-  load8_f32(sums + C + c0, s2);
+  load8_rep(sums + c0, rep, s1);
+  load8_rep(sums + C + c0, rep, s2);
   load8_f32(gamma + c0, g);
   load8_f32(beta + c0, b);
 #pragma unroll
@@ -164,20 +225,48 @@ __device__ __forceinline__ void bn_coeffs8(const float* sums, const float* gamma
   }
 }
 
+__device__ __forceinline__ void bn_coeffs8_from(const float (&s1)[8], const float (&s2)[8], const float* gamma, const float* beta,
+                                                int c0, float invM, float eps, float (&sc)[8], float (&sh)[8]) {
+  float g[8], b[8];
+  load8_f32(gamma + c0, g);
+  load8_f32(beta + c0, b);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const float mean = s1[i] * invM;
+    const float var = fmaxf(s2[i] * invM - mean * mean, 0.f);
+    const float gi = g[i] * rsqrtf(var + eps);
+    sc[i] = gi;
+    sh[i] = b[i] - mean * gi;
+  }
+}
+
+// FOLD: the sums are replicated and added once per block through LDS; a kernel of its own so that the plain form
+// allocates no LDS (it then fits beside workgroups of the convolutions that fill a compute unit's LDS).
+template <bool FOLD>
 __global__ __launch_bounds__(kThreads) void bn_apply_kernel(BnApplyArgs a, int CGB, int rows_per_block) {
   const int C = a.C;
   if (blockIdx.x == 0 && blockIdx.y == 0) {
-    if (a.run_mean) bn_running(a.sums, a.run_mean, a.run_var, C, a.M, a.momentum);
-    if (a.x2 && a.run_mean2) bn_running(a.sums2, a.run_mean2, a.run_var2, C, a.M, a.momentum);
+    if (a.run_mean) bn_running(a.sums, a.rep_stride, a.run_mean, a.run_var, C, a.M, a.momentum);
+    if (a.x2 && a.run_mean2) bn_running(a.sums2, a.rep_stride, a.run_mean2, a.run_var2, C, a.M, a.momentum);
   }
   const int RL = kThreads / CGB;
   const int cg = blockIdx.x * CGB + threadIdx.x % CGB, rl = threadIdx.x / CGB;
   const int c0 = cg * 8;
-  if (c0 >= C) return;
   const float invM = 1.f / (float)a.M;
   float sc[8], sh[8], sc2[8], sh2[8];
-  bn_coeffs8(a.sums, a.gamma, a.beta, C, c0, invM, a.eps, sc, sh);
-  if (a.x2) bn_coeffs8(a.sums2, a.gamma2, a.beta2, C, c0, invM, a.eps, sc2, sh2);
+  if constexpr (FOLD) {
+    const float* const src[4] = {a.sums, a.sums + C, a.x2 ? a.sums2 : a.sums, a.x2 ? a.sums2 + C : a.sums + C};
+    const int rep[4] = {a.rep_stride, a.rep_stride, a.rep_stride, a.rep_stride};
+    float f[4][8];
+    fold_replicas<4>(src, rep, c0, c0 < C, CGB, f);
+    if (c0 >= C) return;
+    bn_coeffs8_from(f[0], f[1], a.gamma, a.beta, c0, invM, a.eps, sc, sh);
+    if (a.x2) bn_coeffs8_from(f[2], f[3], a.gamma2, a.beta2, c0, invM, a.eps, sc2, sh2);
+  } else {
+    if (c0 >= C) return;
+    bn_coeffs8(a.sums, a.rep_stride, a.gamma, a.beta, C, c0, invM, a.eps, sc, sh);
+    if (a.x2) bn_coeffs8(a.sums2, a.rep_stride, a.gamma2, a.beta2, C, c0, invM, a.eps, sc2, sh2);
+  }
   const int row_lo = blockIdx.y * rows_per_block, row_hi = min(a.M, row_lo + rows_per_block);
 #pragma unroll 4
   for (int row = row_lo + rl; row < row_hi; row += RL) {
@@ -220,7 +309,10 @@ hipError_t launch_bn_apply(const BnApplyArgs& a, hipStream_t s) {
   if (!al16(a.sums) || !al16(a.gamma) || !al16(a.beta) || (a.x2 && (!al16(a.sums2) || !al16(a.gamma2) || !al16(a.beta2))))
     return hipErrorInvalidValue;   // per-channel vectors are read 16 bytes at a time
   const ApplyShape r = apply_shape(a.M, a.C);
-  hipLaunchKernelGGL(bn_apply_kernel, r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block);
+  if (a.rep_stride > 0 && r.CGB * kStatReplicas <= 64)
+    hipLaunchKernelGGL(bn_apply_kernel<true>, r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block);
+  else
+    hipLaunchKernelGGL(bn_apply_kernel<false>, r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block);
   return hipGetLastError();
 }
 
@@ -266,8 +358,8 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_reduce_kernel(BnBwdArgs a, in
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int c = cg * 8 + i;
-      const float m = a.sums[c] * invM;
-      const float var = fmaxf(a.sums[C + c] * invM - m * m, 0.f);
+      const float m = load_rep(a.sums + c, a.rep_stride) * invM;
+      const float var = fmaxf(load_rep(a.sums + C + c, a.rep_stride) * invM - m * m, 0.f);
       mu[i] = m;
       iv[i] = rsqrtf(var + a.eps);
     }
@@ -301,23 +393,33 @@ hipError_t launch_bn_bwd_reduce(const BnBwdArgs& a, hipStream_t s) {
 }
 
 // dx = gamma*invstd*(g - S1/M - xhat*S2/M) [+ addend];  dgamma = S2, dbeta = S1
-template <bool DY_F32>
+template <bool DY_F32, bool FOLD>
 __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(BnBwdArgs a, int CGB, int rows_per_block) {
   const int C = a.C;
   const int RL = kThreads / CGB;
   const int cg = blockIdx.x * CGB + threadIdx.x % CGB, rl = threadIdx.x / CGB;
   const int c0 = cg * 8;
-  if (c0 >= C) return;
   const float invM = 1.f / (float)a.M;
   // per channel: xhat = x*is - mean*is;  dx = gi*g - gi*k1 - gi*k2*xhat = gi*g + (pa*x + pb)
   float gi[8], pa[8], pb[8];
   {
     float s1[8], s2[8], gm[8], b1[8], b2[8];
-    load8_f32(a.sums + c0, s1);
-    load8_f32(a.sums + C + c0, s2);
+    if constexpr (FOLD) {   // replicated sums: added once per block through LDS (see bn_apply_kernel)
+      const float* const src[4] = {a.sums, a.sums + C, a.bsums, a.bsums + C};
+      const int rep[4] = {a.rep_stride, a.rep_stride, a.brep_stride, a.brep_stride};
+      float f[4][8];
+      fold_replicas<4>(src, rep, c0, c0 < C, CGB, f);
+      if (c0 >= C) return;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { s1[i] = f[0][i]; s2[i] = f[1][i]; b1[i] = f[2][i]; b2[i] = f[3][i]; }
+    } else {
+      if (c0 >= C) return;
+      load8_rep(a.sums + c0, a.rep_stride, s1);
+      load8_rep(a.sums + C + c0, a.rep_stride, s2);
+      load8_rep(a.bsums + c0, a.brep_stride, b1);
+      load8_rep(a.bsums + C + c0, a.brep_stride, b2);
+    }
     load8_f32(a.gamma + c0, gm);
-    load8_f32(a.bsums + c0, b1);
-    load8_f32(a.bsums + C + c0, b2);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const float mean = s1[i] * invM;
@@ -363,10 +465,14 @@ hipError_t launch_bn_bwd_apply(const BnBwdArgs& a_in, hipStream_t s) {
   if (!al16(a.sums) || !al16(a.gamma) || !al16(a.bsums) || !al16(a.dgamma) || !al16(a.dbeta)) return hipErrorInvalidValue;
   ApplyShape r = apply_shape(a.M, a.C);
   if (!a.out_f32 && !a.out_b16) r.grid.y = 1;   // only dgamma / dbeta
-  if (a.dy_is_f32)
-    hipLaunchKernelGGL(bn_bwd_apply_kernel<true>, r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block);
-  else
-    hipLaunchKernelGGL(bn_bwd_apply_kernel<false>, r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block);
+  const bool fold = (a.rep_stride > 0 || a.brep_stride > 0) && r.CGB * kStatReplicas <= 64;
+  if (a.dy_is_f32) {
+    if (fold) hipLaunchKernelGGL((bn_bwd_apply_kernel<true, true>), r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block);
+    else hipLaunchKernelGGL((bn_bwd_apply_kernel<true, false>), r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block);
+  } else {
+    if (fold) hipLaunchKernelGGL((bn_bwd_apply_kernel<false, true>), r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block);
+    else hipLaunchKernelGGL((bn_bwd_apply_kernel<false, false>), r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block);
+  }
   return hipGetLastError();
 }
 
