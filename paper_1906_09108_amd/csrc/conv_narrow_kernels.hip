@@ -38,11 +38,11 @@ struct NarrowLaunch {
 
 // Output stage: what store_tile does for a same-grid unit-stride output (so the flat pixel index is the output
 // index and no coordinates are needed), with every optional operand of all J pixel blocks requested before the
-// first is used -- one memory round trip instead of one per operand and block -- and the per-channel sums of the
-// four waves added through LDS without atomics (one barrier).
+// first is used -- one memory round trip instead of one per operand and block.  The per-channel sums stay in the
+// caller's registers (s1, s2) until narrow_flush_sums.
 template <int J, int NB, int WN, int CO>
 __device__ __forceinline__ void narrow_store(const GatherConvArgs& a, const f32x4 (&acc)[NB][J], int m_base, int wave, int lane,
-                                             int Mtot) {
+                                             int Mtot, float (&s1)[NB][4], float (&s2)[NB][4]) {
   constexpr int WM = 4 / WN;
   const int wn = wave / WM;
   const int c0 = wn * NB * 16 + 4 * (lane >> 4);   // this lane's first channel of block 0
@@ -81,11 +81,6 @@ __device__ __forceinline__ void narrow_store(const GatherConvArgs& a, const f32x
 #pragma unroll
       for (int i = 0; i < NB; ++i) bx[j][i] = *reinterpret_cast<const uint2*>(a.bnx + o[j] + i * 16);
   }
-  float s1[NB][4], s2[NB][4];
-#pragma unroll
-  for (int i = 0; i < NB; ++i)
-#pragma unroll
-    for (int v = 0; v < 4; ++v) s1[i][v] = s2[i][v] = 0.f;
 #pragma unroll
   for (int j = 0; j < J; ++j)
 #pragma unroll
@@ -125,8 +120,15 @@ __device__ __forceinline__ void narrow_store(const GatherConvArgs& a, const f32x
         }
       }
     }
+}
+
+// The per-channel sums a workgroup gathered over its tiles: over the 16 lanes that hold the same 4 channels, then one
+// slot per wave in LDS, then over the waves, then one atomic per channel and value into this workgroup's copy.
+template <int NB, int WN, int CO>
+__device__ __forceinline__ void narrow_flush_sums(const GatherConvArgs& a, const float (&s1)[NB][4], const float (&s2)[NB][4],
+                                                  int wave, int lane) {
+  constexpr int WM = 4 / WN;
   if (a.stats) {
-    // over the 16 lanes that hold the same 4 channels, then one slot per wave in LDS, then over the waves
     __shared__ float red[4][2][NB * 16];
 #pragma unroll
     for (int i = 0; i < NB; ++i)
@@ -171,21 +173,14 @@ __global__ __launch_bounds__(256) void conv_narrow_kernel(GatherConvArgs a, Narr
   const int wm = wave % WM, wn = wave / WM;
   const int W = a.Wi, H = a.Hi;
   const int Mtot = a.N * H * W;
-  const int m0 = blockIdx.x * TP;
   const int units = L.units;                         // patch row r holds pixel m0 - W - 1 + r
+  const int ntiles = (Mtot + TP - 1) / TP;
 
-  // ---- the patch: one burst of loads, lane i of a round lands at unit position base + i ----
-  for (int base = wave * 64; base < units; base += 256) {
-    const int pos = base + lane;
-    const int r = pos / U, us = pos % U;             // stored position -> row and swizzled unit
-    const int u = us ^ ((r >> SWZ_SHIFT) & (U - 1));
-    int q = m0 - W - 1 + r;                          // rows that do not exist read some row that does: nothing valid refers to them
-    q = q < 0 ? 0 : (q >= Mtot ? Mtot - 1 : q);
-    narrow_dma16(a.in + (size_t)q * CI + u * 8, smem + (size_t)base * 16);
-  }
   if (tid < 8) reinterpret_cast<uint4*>(smem + (size_t)units * 16)[tid] = make_uint4(0u, 0u, 0u, 0u);
 
-  // ---- the filter: fragment (s, nb) = rows 16 nb .. +15 of this wave's channels, k = 32 s + 8 (lane >> 4) .. +7 ----
+  // ---- the filter: fragment (s, nb) = rows 16 nb .. +15 of this wave's channels, k = 32 s + 8 (lane >> 4) .. +7.
+  //      Loaded once; a workgroup then takes tiles blockIdx.x, blockIdx.x + gridDim.x, ... (with 64 channels and
+  //      many pixels the filter, 144 registers per lane, would otherwise be most of what the kernel reads) ----
   bf16x8 wf[S][NB];
   {
     const int g = lane >> 4;
@@ -200,61 +195,81 @@ __global__ __launch_bounds__(256) void conv_narrow_kernel(GatherConvArgs a, Narr
         wf[s][nb] = __builtin_bit_cast(bf16x8, v);
       }
   }
-
-  // ---- LDS address of this lane's pixel fragment for every pixel block and step.  With 64 channels the two steps
-  //      of a tap differ by unit bit 2 = address bit 6 (the zero area is 128 bytes for that), so one address
-  //      serves both ----
-  constexpr int SA = CI == 64 ? 9 : S;
-  const unsigned zero_addr = (unsigned)units * 16u;
-  unsigned xaddr[J][SA];
-  {
-    const int g = lane >> 4;
-#pragma unroll
-    for (int j = 0; j < J; ++j) {
-      const int pl = (wm * J + j) * 16 + (lane & 15);
-      const int m = m0 + pl;
-      const bool inside = m < Mtot;
-      const int row = narrow_div(m, L.magic_w), ow = m - row * W;   // image row over the whole batch, column
-      const int oh = row - narrow_div(row, L.magic_h) * H;
-#pragma unroll
-      for (int s = 0; s < SA; ++s) {
-        // which tap and which unit of the pixel this lane's 8 k values are
-        const int slot = CI == 16 ? 2 * s + (g >> 1) : s;
-        const int u = CI == 16 ? (g & 1) : g;
-        unsigned addr = zero_addr;
-        if (slot < 9) {
-          const int tp = a.tap[slot];
-          const int dh = (tp & 0xff) - 8, dw = ((tp >> 8) & 0xff) - 8;
-          const bool ok = inside && (unsigned)(oh + dh) < (unsigned)H && (unsigned)(ow + dw) < (unsigned)W;
-          const int r = pl + W + 1 + dh * W + dw;
-          if (ok) addr = (unsigned)(r * ROWB + ((u ^ ((r >> SWZ_SHIFT) & (U - 1))) << 4));
-        }
-        xaddr[j][s] = addr;
-      }
-    }
-  }
-
-  f32x4 acc[NB][J];
+  float s1[NB][4], s2[NB][4];   // per-channel sums of this lane's outputs over all tiles (only with a.stats)
 #pragma unroll
   for (int i = 0; i < NB; ++i)
 #pragma unroll
-    for (int j = 0; j < J; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int v = 0; v < 4; ++v) s1[i][v] = s2[i][v] = 0.f;
 
-  __builtin_amdgcn_s_waitcnt(0);   // every load of this wave has landed (patch in LDS, filter in registers)
-  __syncthreads();
+  constexpr int SA = CI == 64 ? 9 : S;
+  const unsigned zero_addr = (unsigned)units * 16u;
+  for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    const int m0 = tile * TP;
+    if (tile != (int)blockIdx.x) __syncthreads();    // every wave is done reading the previous tile's patch
 
-#pragma unroll
-  for (int j = 0; j < J; ++j)
-#pragma unroll
-    for (int s = 0; s < S; ++s) {
-      const unsigned addr = CI == 64 ? (xaddr[j][s >> 1] ^ ((s & 1) << 6)) : xaddr[j][s];
-      const bf16x8 b = *reinterpret_cast<const bf16x8*>(smem + addr);
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) acc[nb][j] = mfma16(wf[s][nb], b, acc[nb][j]);
+    // ---- the patch: one burst of loads, lane i of a round lands at unit position base + i ----
+    for (int base = wave * 64; base < units; base += 256) {
+      const int pos = base + lane;
+      const int r = pos / U, us = pos % U;           // stored position -> row and swizzled unit
+      const int u = us ^ ((r >> SWZ_SHIFT) & (U - 1));
+      int q = m0 - W - 1 + r;                        // rows that do not exist read some row that does: nothing valid refers to them
+      q = q < 0 ? 0 : (q >= Mtot ? Mtot - 1 : q);
+      narrow_dma16(a.in + (size_t)q * CI + u * 8, smem + (size_t)base * 16);
     }
 
-  (void)wn;
-  narrow_store<J, NB, WN, CO>(a, acc, m0 + wm * J * 16, wave, lane, Mtot);
+    // ---- LDS address of this lane's pixel fragment for every pixel block and step.  With 64 channels the two
+    //      steps of a tap differ by unit bit 2 = address bit 6 (the zero area is 128 bytes for that), so one
+    //      address serves both ----
+    unsigned xaddr[J][SA];
+    {
+      const int g = lane >> 4;
+#pragma unroll
+      for (int j = 0; j < J; ++j) {
+        const int pl = (wm * J + j) * 16 + (lane & 15);
+        const int m = m0 + pl;
+        const bool inside = m < Mtot;
+        const int row = narrow_div(m, L.magic_w), ow = m - row * W;   // image row over the whole batch, column
+        const int oh = row - narrow_div(row, L.magic_h) * H;
+#pragma unroll
+        for (int s = 0; s < SA; ++s) {
+          // which tap and which unit of the pixel this lane's 8 k values are
+          const int slot = CI == 16 ? 2 * s + (g >> 1) : s;
+          const int u = CI == 16 ? (g & 1) : g;
+          unsigned addr = zero_addr;
+          if (slot < 9) {
+            const int tp = a.tap[slot];
+            const int dh = (tp & 0xff) - 8, dw = ((tp >> 8) & 0xff) - 8;
+            const bool ok = inside && (unsigned)(oh + dh) < (unsigned)H && (unsigned)(ow + dw) < (unsigned)W;
+            const int r = pl + W + 1 + dh * W + dw;
+            if (ok) addr = (unsigned)(r * ROWB + ((u ^ ((r >> SWZ_SHIFT) & (U - 1))) << 4));
+          }
+          xaddr[j][s] = addr;
+        }
+      }
+    }
+
+    f32x4 acc[NB][J];
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+      for (int j = 0; j < J; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    __builtin_amdgcn_s_waitcnt(0);   // every load of this wave has landed (patch in LDS, filter in registers)
+    __syncthreads();
+
+#pragma unroll
+    for (int j = 0; j < J; ++j)
+#pragma unroll
+      for (int s = 0; s < S; ++s) {
+        const unsigned addr = CI == 64 ? (xaddr[j][s >> 1] ^ ((s & 1) << 6)) : xaddr[j][s];
+        const bf16x8 b = *reinterpret_cast<const bf16x8*>(smem + addr);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) acc[nb][j] = mfma16(wf[s][nb], b, acc[nb][j]);
+      }
+
+    narrow_store<J, NB, WN, CO>(a, acc, m0 + wm * J * 16, wave, lane, Mtot, s1, s2);
+  }
+  narrow_flush_sums<NB, WN, CO>(a, s1, s2, wave, lane);
 }
 
 template <int CI, int NB, int WN, int J>
@@ -278,7 +293,8 @@ hipError_t run_narrow(const GatherConvArgs& a, hipStream_t s) {
   L.units = units;
   L.magic_w = ((1ull << 40) + a.Wi - 1) / a.Wi;
   L.magic_h = ((1ull << 40) + a.Hi - 1) / a.Hi;
-  hipLaunchKernelGGL((conv_narrow_kernel<CI, NB, WN, J>), dim3((Mtot + TP - 1) / TP), dim3(256), lds, s, a, L);
+  const int ntiles = (Mtot + TP - 1) / TP;
+  hipLaunchKernelGGL((conv_narrow_kernel<CI, NB, WN, J>), dim3(ntiles < 512 ? ntiles : 512), dim3(256), lds, s, a, L);
   return hipGetLastError();
 }
 

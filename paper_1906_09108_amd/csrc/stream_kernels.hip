@@ -317,16 +317,6 @@ hipError_t launch_bn_apply(const BnApplyArgs& a, hipStream_t s) {
 }
 
 // ---- BN backward ---------------------------------------------------------------------------------
-// mean / invstd per channel from the forward sums, into LDS
-__device__ __forceinline__ void bn_moments(const float* sums, int C, float invM, float eps, float* mean, float* is) {
-  for (int c = threadIdx.x; c < C; c += blockDim.x) {
-    const float mu = sums[c] * invM;
-    const float var = fmaxf(sums[C + c] * invM - mu * mu, 0.f);
-    mean[c] = mu;
-    is[c] = rsqrtf(var + eps);
-  }
-}
-
 template <bool DY_F32>
 __device__ __forceinline__ void load_masked_dy(const void* dy, const bf16_t* mask, size_t o, float (&g)[8]) {
   if (DY_F32)
