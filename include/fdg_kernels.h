@@ -49,9 +49,16 @@ int fdgk_conv_dgrad(const void* dy_b16, const void* wt_b16, const float* addend_
  *   dx = gate > 0 ? (data gradient + addend) : 0,
  *   gsums[i] += sum over pixels of bf16(dx[..,i]),  gsums[cip+i] += sum of bf16(dx[..,i]) * bnx[..,i]
  * (gsums_f32 [2*cip], zero it first): the two reductions of the batch-norm backward, taken in the output stage of the
- * convolution instead of a pass of their own.  Only the wide kernels do this: fdgk_conv_dgrad_gates says (1 / 0) whether
- * a shape is covered, fdgk_conv_dgrad_gated returns hipErrorInvalidValue (1) where it is not.                       */
+ * convolution instead of a pass of their own.  The wide kernels and the narrow kernel do this: fdgk_conv_dgrad_gates
+ * says (1 / 0) whether a shape is covered, fdgk_conv_dgrad_gated returns hipErrorInvalidValue (1) where it is not.  */
 int fdgk_conv_dgrad_gates(int n, int h, int w, int ci, int co, int ksize, int stride);
+/* The same for the last data gradient of a block, whose fp32 result plus the shortcut gradient (addend, counted where
+ * addmask > 0) is the gradient at the output of the layer BELOW: gate_b16 = that layer's output, bnx_b16 = the input
+ * of that layer's last batch norm, and the two sums are taken from the fp32 values (dx_f32 is required; it is what
+ * that batch norm's backward reads).  Narrow layers only (16 / 32 / 64 channels in and out, 3x3, stride 1); 1 elsewhere. */
+int fdgk_conv_dgrad_feeding_next(const void* dy_b16, const void* wt_b16, const float* addend_f32, const void* addmask_b16,
+                                 const void* gate_b16, const void* bnx_b16, float* gsums_f32, float* dx_f32, void* dx_b16,
+                                 int n, int h, int w, int ci, int co, int ksize, int stride, void* hip_stream);
 int fdgk_conv_dgrad_gated(const void* dy_b16, const void* wt_b16, const float* addend_f32, const void* gate_b16,
                           const void* bnx_b16, float* gsums_f32, float* dx_f32, void* dx_b16, int n, int h, int w, int ci,
                           int co, int ksize, int stride, void* hip_stream);

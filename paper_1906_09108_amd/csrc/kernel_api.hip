@@ -46,6 +46,18 @@ int fdgk_conv_dgrad_gated(const void* dy_b16, const void* wt_b16, const float* a
                                static_cast<bf16_t*>(dx_b16), st(hip_stream));
 }
 
+int fdgk_conv_dgrad_feeding_next(const void* dy_b16, const void* wt_b16, const float* addend_f32, const void* addmask_b16,
+                                 const void* gate_b16, const void* bnx_b16, float* gsums_f32, float* dx_f32, void* dx_b16,
+                                 int n, int h, int w, int ci, int co, int ksize, int stride, void* hip_stream) {
+  ConvShape c;
+  if (!dy_b16 || !wt_b16 || !gate_b16 || !bnx_b16 || !gsums_f32 || !dx_f32 || !conv_shape(c, n, h, w, ci, co, ksize, stride))
+    return (int)hipErrorInvalidValue;
+  return (int)conv_dgrad_feeding_next(c, static_cast<const bf16_t*>(dy_b16), static_cast<const bf16_t*>(wt_b16), addend_f32,
+                                      static_cast<const bf16_t*>(addmask_b16), static_cast<const bf16_t*>(gate_b16),
+                                      static_cast<const bf16_t*>(bnx_b16), gsums_f32, dx_f32, static_cast<bf16_t*>(dx_b16),
+                                      st(hip_stream));
+}
+
 int fdgk_conv_dgrad_gates(int n, int h, int w, int ci, int co, int ksize, int stride) {
   ConvShape c;
   return conv_shape(c, n, h, w, ci, co, ksize, stride) && conv_dgrad_gates(c) ? 1 : 0;

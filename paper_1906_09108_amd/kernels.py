@@ -6,7 +6,7 @@ import ctypes
 
 from .binding import _ptr, _stream_handle, load
 
-KERNEL_EXPORTS = ["fdgk_conv_fwd", "fdgk_conv_dgrad", "fdgk_conv_dgrad_gated", "fdgk_conv_dgrad_gates", "fdgk_bn_bwd_gated", "fdgk_conv_wgrad", "fdgk_conv_wgrad_scratch_bytes", "fdgk_bn_stats", "fdgk_bn_apply",
+KERNEL_EXPORTS = ["fdgk_conv_fwd", "fdgk_conv_dgrad", "fdgk_conv_dgrad_gated", "fdgk_conv_dgrad_feeding_next", "fdgk_conv_dgrad_gates", "fdgk_bn_bwd_gated", "fdgk_conv_wgrad", "fdgk_conv_wgrad_scratch_bytes", "fdgk_bn_stats", "fdgk_bn_apply",
                   "fdgk_bn_bwd", "fdgk_sgd"]
 _ready = False
 
@@ -19,6 +19,7 @@ def _lib():
         lib.fdgk_conv_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
         lib.fdgk_conv_dgrad.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
         lib.fdgk_conv_dgrad_gated.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
+        lib.fdgk_conv_dgrad_feeding_next.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
         lib.fdgk_conv_dgrad_gates.argtypes = [i, i, i, i, i, i, i]
         lib.fdgk_bn_bwd_gated.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, f, vp]
         lib.fdgk_conv_wgrad.argtypes = [vp, vp, vp, vp, sz, i, i, i, i, i, i, i, i, vp]
@@ -28,6 +29,8 @@ def _lib():
         lib.fdgk_bn_bwd.argtypes = [vp, i, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, f, vp]
         lib.fdgk_sgd.argtypes = [vp, vp, vp, sz, f, f, f, vp]
         for n in KERNEL_EXPORTS:
+            if getattr(lib, n).argtypes is None:   # a pointer passed without a declared type would be cut to 32 bits
+                raise RuntimeError(f"{n}: argument types not declared")
             getattr(lib, n).restype = i
         lib.fdgk_conv_wgrad_scratch_bytes.restype = sz
         _ready = True
@@ -58,6 +61,13 @@ def fdgk_conv_dgrad_gated(dy_b16, wt_b16, addend_f32, gate_b16, bnx_b16, gsums_f
     _ok(_lib().fdgk_conv_dgrad_gated(_ptr(dy_b16), _ptr(wt_b16), _ptr(addend_f32), _ptr(gate_b16), _ptr(bnx_b16),
                                      _ptr(gsums_f32), _ptr(dx_f32), _ptr(dx_b16), n, h, w, ci, co, ksize, stride,
                                      _stream_handle(stream)), "fdgk_conv_dgrad_gated")
+
+
+def fdgk_conv_dgrad_feeding_next(dy_b16, wt_b16, addend_f32, addmask_b16, gate_b16, bnx_b16, gsums_f32, dx_f32, dx_b16, n, h, w,
+                                 ci, co, ksize, stride, stream=None):
+    _ok(_lib().fdgk_conv_dgrad_feeding_next(_ptr(dy_b16), _ptr(wt_b16), _ptr(addend_f32), _ptr(addmask_b16), _ptr(gate_b16),
+                                            _ptr(bnx_b16), _ptr(gsums_f32), _ptr(dx_f32), _ptr(dx_b16), n, h, w, ci, co, ksize,
+                                            stride, _stream_handle(stream)), "fdgk_conv_dgrad_feeding_next")
 
 
 def fdgk_bn_bwd_gated(g_b16, x_b16, sums_f32, gamma, gsums_f32, addend_f32, dx_f32, dx_b16, dgamma, dbeta, m, c, eps,

@@ -235,6 +235,44 @@ def test_gated_data_gradient_feeds_the_batch_norm_backward(case):
     assert rel(dx16.to(t.float32).cpu().numpy(), dref) <= B16_TOL
 
 
+@pytest.mark.parametrize("case", [(3, 7, 5, 16, 16, 3, 1), (16, 32, 32, 16, 16, 3, 1), (4, 16, 16, 32, 32, 3, 1), (3, 8, 8, 64, 64, 3, 1),
+                                  (9, 64, 64, 64, 64, 3, 1)])
+def test_data_gradient_that_feeds_the_layer_below(case):
+    """conv_dgrad_feeding_next: g = gate > 0 ? dgrad + addend * [addmask > 0] : 0 in fp32 (and its bf16 copy), and the
+    sums [sum g, sum g * x] of the FP32 values.  Reference: the oracle's data gradient, gate and mask applied in numpy."""
+    from paper_1906_09108_amd import kernels as K
+    t = _torch()
+    n, h, w, ci, co, k, s = case
+    print("dgrad feeding next", case, flush=True)
+    x_unused, wt, dy, ho, wo = _conv_data(case, 21)
+    r = np.random.default_rng(22)
+    ref = K32.conv_bwd_data(dy, wt, x_unused.shape, s, 1).astype(np.float64)
+    add = r.standard_normal(ref.shape).astype(np.float32) * 0.5
+    mask = bf16_round(np.maximum(r.standard_normal(ref.shape), 0))
+    gate = bf16_round(np.maximum(r.standard_normal(ref.shape), 0))
+    bnx = bf16_round(r.standard_normal(ref.shape) * (0.5 + r.random((1, ci, 1, 1))) + r.standard_normal((1, ci, 1, 1)))
+    wtd = t.from_numpy(wt.transpose(1, 2, 3, 0).copy()).to(t.bfloat16).contiguous().cuda()
+    gsums = t.zeros(2 * ci, dtype=t.float32, device="cuda")
+    g32 = t.full((n, h, w, ci), float("nan"), dtype=t.float32, device="cuda")
+    g16 = t.zeros((n, h, w, ci), dtype=t.bfloat16, device="cuda")
+    K.fdgk_conv_dgrad_feeding_next(to_dev_nhwc_b16(dy), wtd, to_dev_nhwc_f32(add), to_dev_nhwc_b16(mask), to_dev_nhwc_b16(gate),
+                                   to_dev_nhwc_b16(bnx), gsums, g32, g16, n, h, w, ci, co, k, s)
+    t.cuda.synchronize()
+    g_ref = (ref + add * (mask > 0)) * (gate > 0)
+    got32 = nhwc_to_nchw(g32)
+    assert rel(got32, g_ref) <= F32_TOL
+    assert rel(nhwc_to_nchw(g16), g_ref) <= B16_TOL
+    assert np.all(got32[gate <= 0] == 0)
+    gf = g32.to(t.float64).reshape(-1, ci).cpu().numpy()
+    xb = to_dev_nhwc_b16(bnx).to(t.float64).reshape(-1, ci).cpu().numpy()
+    got = gsums.cpu().numpy().astype(np.float64)
+    assert rel(got[:ci], gf.sum(0)) <= 1e-5
+    assert rel(got[ci:], (gf * xb).sum(0)) <= 1e-5
+    # and they are NOT the sums of the bf16 copy wherever the two differ measurably
+    gb = g16.to(t.float64).reshape(-1, ci).cpu().numpy()
+    assert np.abs(got[ci:] - (gf * xb).sum(0)).max() <= np.abs(got[ci:] - (gb * xb).sum(0)).max() + 1e-3 * np.abs(got[ci:]).max()
+
+
 def test_gated_data_gradient_refuses_layers_without_such_a_kernel():
     """Neither the wide kernels nor the narrow one take a 24 -> 40 layer or a stride-2 16 -> 32 layer."""
     from paper_1906_09108_amd import kernels as K

@@ -26,6 +26,7 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == set(binding.EXPORTS)
     knames = _declared("fdg_kernels.h", "fdgk_")
     assert set(knames) == set(kernels.KERNEL_EXPORTS)
+    kernels._lib()   # raises if an exported kernel entry has no declared argument types (pointers would be cut to 32 bits)
     for n in names + knames:
         assert getattr(lib, n) is not None
 
