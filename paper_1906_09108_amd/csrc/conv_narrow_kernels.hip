@@ -26,6 +26,14 @@ __device__ __forceinline__ void narrow_dma16(const void* gsrc, void* lds_wave_ba
                                    (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
 }
 
+// Workgroups are dealt to the 8 XCDs round robin (XCD = block index mod 8).  The inverse numbering: the blocks that
+// run on one XCD get consecutive logical indices, so that neighbouring tiles -- which share their halo rows -- are
+// fetched through the same L2.
+__device__ __forceinline__ int narrow_xcd_consecutive(int block, int total) {
+  const int base = total >> 3, rem = total & 7, x = block & 7, q = block >> 3;
+  return x * base + (x < rem ? x : rem) + q;
+}
+
 // n / d for n < 2^30 and d <= 1024 with one 64-bit multiply: magic = ceil(2^40 / d) (exact: the error term
 // n * (magic * d - 2^40) stays below 2^40)
 __device__ __forceinline__ int narrow_div(int n, unsigned long long magic) {
@@ -34,6 +42,7 @@ __device__ __forceinline__ int narrow_div(int n, unsigned long long magic) {
 struct NarrowLaunch {
   int units;                        // 16-byte units of patch in LDS (a multiple of 256)
   unsigned long long magic_w, magic_h;
+  int same_masks;                   // a workgroup's tiles are whole images apart: the tap masks of its first tile hold for all
 };
 
 // Output stage: what store_tile does for a same-grid unit-stride output (so the flat pixel index is the output
@@ -158,8 +167,8 @@ __device__ __forceinline__ void narrow_flush_sums(const GatherConvArgs& a, const
 }
 
 // CI input channels; a wave owns J blocks of 16 pixels and NB blocks of 16 output channels; WN waves side by side
-// over the output channels (Co = 16 * NB * WN), 4 / WN over the pixels.  LDS: `units` 16-byte units of patch
-// (a multiple of 256: whole load rounds of the workgroup) followed by 128 bytes of zeros.
+// over the output channels (Co = 16 * NB * WN), 4 / WN over the pixels.  LDS: two patch buffers, each `units` 16-byte
+// units of patch (a multiple of 256: whole load rounds of the workgroup) followed by 128 bytes of zeros.
 template <int CI, int NB, int WN, int J>
 __global__ __launch_bounds__(256) void conv_narrow_kernel(GatherConvArgs a, NarrowLaunch L) {
   constexpr int WM = 4 / WN, TP = 16 * J * WM, CO = 16 * NB * WN;
@@ -176,7 +185,8 @@ __global__ __launch_bounds__(256) void conv_narrow_kernel(GatherConvArgs a, Narr
   const int units = L.units;                         // patch row r holds pixel m0 - W - 1 + r
   const int ntiles = (Mtot + TP - 1) / TP;
 
-  if (tid < 8) reinterpret_cast<uint4*>(smem + (size_t)units * 16)[tid] = make_uint4(0u, 0u, 0u, 0u);
+  const unsigned bufs = (unsigned)units * 16u + 128u;   // bytes of one patch buffer: the patch, then 128 bytes of zeros
+  if (tid < 16) reinterpret_cast<uint4*>(smem + (size_t)(tid >> 3) * bufs + (size_t)units * 16)[tid & 7] = make_uint4(0u, 0u, 0u, 0u);
 
   // ---- the filter: fragment (s, nb) = rows 16 nb .. +15 of this wave's channels, k = 32 s + 8 (lane >> 4) .. +7.
   //      Loaded once; a workgroup then takes tiles blockIdx.x, blockIdx.x + gridDim.x, ... (with 64 channels and
@@ -203,25 +213,30 @@ __global__ __launch_bounds__(256) void conv_narrow_kernel(GatherConvArgs a, Narr
 
   constexpr int SA = CI == 64 ? 9 : S;
   const unsigned zero_addr = (unsigned)units * 16u;
-  for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+  unsigned xaddr[J][SA];
+  const int first_tile = narrow_xcd_consecutive(blockIdx.x, gridDim.x);
+  // the patch of a tile: one burst of loads, lane i of a round lands at unit position base + i of buffer `buf`
+  auto issue_patch = [&](int tile, int buf) {
     const int m0 = tile * TP;
-    if (tile != (int)blockIdx.x) __syncthreads();    // every wave is done reading the previous tile's patch
-
-    // ---- the patch: one burst of loads, lane i of a round lands at unit position base + i ----
     for (int base = wave * 64; base < units; base += 256) {
       const int pos = base + lane;
       const int r = pos / U, us = pos % U;           // stored position -> row and swizzled unit
       const int u = us ^ ((r >> SWZ_SHIFT) & (U - 1));
       int q = m0 - W - 1 + r;                        // rows that do not exist read some row that does: nothing valid refers to them
       q = q < 0 ? 0 : (q >= Mtot ? Mtot - 1 : q);
-      narrow_dma16(a.in + (size_t)q * CI + u * 8, smem + (size_t)base * 16);
+      narrow_dma16(a.in + (size_t)q * CI + u * 8, smem + (size_t)buf * bufs + (size_t)base * 16);
     }
+  };
+  // Two patch buffers: while the MFMAs of a tile run, the patch of the workgroup's next tile is already on its way.
+  if (first_tile < ntiles) issue_patch(first_tile, 0);
+  int cur = 0;
+  for (int tile = first_tile; tile < ntiles; tile += gridDim.x) {
+    const int m0 = tile * TP;
 
     // ---- LDS address of this lane's pixel fragment for every pixel block and step.  With 64 channels the two
     //      steps of a tap differ by unit bit 2 = address bit 6 (the zero area is 128 bytes for that), so one
     //      address serves both ----
-    unsigned xaddr[J][SA];
-    {
+    if (tile == first_tile || !L.same_masks) {
       const int g = lane >> 4;
 #pragma unroll
       for (int j = 0; j < J; ++j) {
@@ -254,20 +269,23 @@ __global__ __launch_bounds__(256) void conv_narrow_kernel(GatherConvArgs a, Narr
 #pragma unroll
       for (int j = 0; j < J; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    __builtin_amdgcn_s_waitcnt(0);   // every load of this wave has landed (patch in LDS, filter in registers)
-    __syncthreads();
+    __builtin_amdgcn_s_waitcnt(0);   // every load of this wave has landed (this tile's patch in LDS, the filter in registers)
+    __syncthreads();                 // ... of every wave; and every wave is done reading the other buffer
+    if (tile + (int)gridDim.x < ntiles) issue_patch(tile + gridDim.x, cur ^ 1);
 
+    const unsigned char* patch = smem + (size_t)cur * bufs;
 #pragma unroll
     for (int j = 0; j < J; ++j)
 #pragma unroll
       for (int s = 0; s < S; ++s) {
         const unsigned addr = CI == 64 ? (xaddr[j][s >> 1] ^ ((s & 1) << 6)) : xaddr[j][s];
-        const bf16x8 b = *reinterpret_cast<const bf16x8*>(smem + addr);
+        const bf16x8 b = *reinterpret_cast<const bf16x8*>(patch + addr);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) acc[nb][j] = mfma16(wf[s][nb], b, acc[nb][j]);
       }
 
     narrow_store<J, NB, WN, CO>(a, acc, m0 + wm * J * 16, wave, lane, Mtot, s1, s2);
+    cur ^= 1;
   }
   narrow_flush_sums<NB, WN, CO>(a, s1, s2, wave, lane);
 }
@@ -278,7 +296,7 @@ hipError_t run_narrow(const GatherConvArgs& a, hipStream_t s) {
   const int Mtot = a.N * a.OH * a.OW;
   const int rows = TP + 2 * a.Wi + 2;
   const int units = (rows * U + 255) / 256 * 256;
-  const size_t lds = (size_t)units * 16 + 128;
+  const size_t lds = 2 * ((size_t)units * 16 + 128);   // two patch buffers, each followed by its zero area
   static bool configured = false;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_narrow_kernel<CI, NB, WN, J>),
@@ -293,8 +311,9 @@ hipError_t run_narrow(const GatherConvArgs& a, hipStream_t s) {
   L.units = units;
   L.magic_w = ((1ull << 40) + a.Wi - 1) / a.Wi;
   L.magic_h = ((1ull << 40) + a.Hi - 1) / a.Hi;
-  const int ntiles = (Mtot + TP - 1) / TP;
-  hipLaunchKernelGGL((conv_narrow_kernel<CI, NB, WN, J>), dim3(ntiles < 512 ? ntiles : 512), dim3(256), lds, s, a, L);
+  const int ntiles = (Mtot + TP - 1) / TP, grid = ntiles < 512 ? ntiles : 512;
+  L.same_masks = ((long long)grid * TP) % ((long long)a.Hi * a.Wi) == 0 ? 1 : 0;
+  hipLaunchKernelGGL((conv_narrow_kernel<CI, NB, WN, J>), dim3(grid), dim3(256), lds, s, a, L);
   return hipGetLastError();
 }
 
@@ -396,8 +415,9 @@ __global__ __launch_bounds__(256) void conv_wgrad_narrow_kernel(WgradArgs a, Nar
   const int g = lane >> 4, i16 = lane & 15;
   const unsigned dy0 = (unsigned)L.xunits * 16u;
   constexpr int TB = C == 16 ? 9 : 3;                // taps whose fragments are read in one batch
-  for (int tile = blockIdx.x; tile < L.tiles; tile += gridDim.x) {
-    if (tile != (int)blockIdx.x) __syncthreads();      // every wave is done reading the previous tile
+  const int first_tile = narrow_xcd_consecutive(blockIdx.x, gridDim.x);
+  for (int tile = first_tile; tile < L.tiles; tile += gridDim.x) {
+    if (tile != first_tile) __syncthreads();           // every wave is done reading the previous tile
     pr0 = tile * L.R;
     fill(a.x, L.xunits, 1, pr0 - 1, L.R + 2, 0);
     fill(a.dy, L.dyunits, 0, pr0, L.R, L.xunits);
@@ -536,9 +556,9 @@ bool conv_narrow_applies(const GatherConvArgs& a) {
     const int dh = (a.tap[i] & 0xff) - 8, dw = ((a.tap[i] >> 8) & 0xff) - 8;
     if (dh < -1 || dh > 1 || dw < -1 || dw > 1 || (a.tap[i] >> 16) != i) return false;
   }
-  // the patch of the largest tile in LDS (two workgroups per compute unit at least)
+  // two patch buffers of the largest tile in LDS, within the 96 KB the kernels are configured for
   const int tp_max = a.Ci == 64 ? 128 : 256;
-  if (((size_t)(tp_max + 2 * a.Wi + 2) * (a.Ci / 8) + 256) * 16 > 64 * 1024) return false;
+  if (2 * ((((size_t)(tp_max + 2 * a.Wi + 2) * (a.Ci / 8) + 255) / 256 * 256) * 16 + 128) > 96 * 1024) return false;
   return true;
 }
 
