@@ -297,11 +297,11 @@ class FdgChain:
     """K modules run as Algorithm I (include/fdg_chain.h).  Owns the modules' workspaces, the mailbox memory and
     the chain handle; step() is one C call."""
 
-    def __init__(self, specs: Sequence, device="cuda:0"):
+    def __init__(self, specs: Sequence, device="cuda:0", save_mode=FDG_SAVE_ACTIVATIONS):
         import torch
         self.torch = torch
         self.device = torch.device(device)
-        self.modules = [FdgModule(sp, device) for sp in specs]
+        self.modules = [FdgModule(sp, device, save_mode=save_mode) for sp in specs]
         self.K = len(self.modules)
         self._handles = (ctypes.c_void_p * self.K)(*[m.handle for m in self.modules])
         nbytes = int(load().fdg_chain_mailbox_bytes(self._handles, self.K))

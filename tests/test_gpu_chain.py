@@ -27,6 +27,11 @@ def _torch():
     return torch
 
 
+def FdgChain_workspace(spec):
+    from paper_1906_09108_amd import binding
+    return binding.fdg_module_workspace_bytes(spec)
+
+
 def _set_params(chain, specs, seed=0):
     thetas = [W.make_params(sp, seed + 17 * k, perturb_bn=True) for k, sp in enumerate(specs)]
     mods = chain.modules if hasattr(chain, "modules") else chain.mods
@@ -35,14 +40,19 @@ def _set_params(chain, specs, seed=0):
     return thetas
 
 
-@pytest.mark.parametrize("K", [1, 2, 3])
-def test_chain_against_the_oracle(K):
+@pytest.mark.parametrize("K,save_mode", [(1, 0), (2, 0), (3, 0), (3, 1)])
+def test_chain_against_the_oracle(K, save_mode):
+    """save_mode 1: every module keeps a saved forward as input + weight snapshot and replays it (include/fdg.h); the
+    lower modules hold 2(K-1-k) of them, which is where that form saves memory."""
     t = _torch()
     from oracle.fdg_oracle import OracleChain
     from paper_1906_09108_amd import FdgChain
-    print("chain parity K =", K, flush=True)
+    print("chain parity K =", K, "save mode", save_mode, flush=True)
     specs = W.chain_specs(K, n=16, width=16, hw=8, blocks=1, beta=0.5)
-    gpu = FdgChain(specs)
+    gpu = FdgChain(specs, save_mode=save_mode)
+    if save_mode:
+        assert sum(m.workspace_bytes for m in gpu.modules) < sum(
+            FdgChain_workspace(sp) for sp in specs)
     same, plain = OracleChain(specs, np.float32, storage="bf16"), OracleChain(specs, np.float32, storage="fp32")
     for ch in (gpu, same, plain):
         _set_params(ch, specs)
