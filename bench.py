@@ -37,6 +37,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..5 (default 4: WRN-28-10 top module)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--two-streams", action="store_true",
+                    help="forward on one stream, delayed backward + update on another (modules with delay >= 1: the two touch "
+                         "different saved forwards and overlap on the GPU)")
     ap.add_argument("--replay", action="store_true",
                     help="FDG_SAVE_INPUT_AND_REPLAY: a saved forward is its input and weight snapshot; the backward runs the forward again")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -152,7 +155,26 @@ def main():
     for t in range(spec.delay):                       # fill the history ring
         mod.forward(xs[t % pool], labels[t % pool], y, stream)
 
+    two = bool(args.two_streams)
+    if two and (spec.delay < 1 or args.replay):
+        print("--two-streams needs a module with delay >= 1 in the stored form", file=sys.stderr)
+        sys.exit(2)
+    if two:
+        s_fwd, s_bwd = torch.cuda.Stream(), torch.cuda.Stream()
+        ev_fwd, ev_upd = torch.cuda.Event(), torch.cuda.Event()
+        torch.cuda.synchronize()
+        ev_upd.record(s_bwd)
+
     def step(i):
+        if two:
+            s_fwd.wait_event(ev_upd)                      # the forward reads the weights of the last update
+            mod.forward(xs[i % pool], labels[i % pool], y, s_fwd)
+            ev_fwd.record(s_fwd)
+            mod.backward_delayed(gs[i % pool], grad_in, s_bwd)   # the oldest saved forward: independent of the one above
+            s_bwd.wait_event(ev_fwd)                      # the update must not move the weights under the forward's snapshot
+            mod.update(lr, s_bwd)
+            ev_upd.record(s_bwd)
+            return
         mod.forward(xs[i % pool], labels[i % pool], y, stream)
         mod.backward_delayed(gs[i % pool], grad_in, stream)
         mod.update(lr, stream)
@@ -223,6 +245,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": spec.name, "batch": spec.n, "delay": spec.delay, "beta": spec.beta,
                    "saved_forward": "input + weight snapshot, replayed by the backward" if args.replay else "activations",
+                   "streams": "forward on one, delayed backward + update on another" if args.two_streams else "one",
                    "workspace_MiB": mod.workspace_bytes / 2 ** 20,
                    "params": W.param_count(spec), "useful_conv_gflop_per_step": W.conv_flops(spec) / 1e9},
         "step_tflops": W.conv_flops(spec) / (ms_per_step * 1e-3) / 1e12,

@@ -23,6 +23,14 @@
  *   - Errors are status codes; nothing throws or aborts.  Argument and queue errors are detected
  *     before anything is enqueued, so a failed call leaves the module unchanged.
  *   - A module object is not thread safe; calls on one module must be serialised by the caller.
+ *   - Two streams.  The forward of the newest batch and the delayed backward of the oldest one touch different
+ *     contexts (Fig. 1(b)) -- that independence is what the method is about -- and share no temporary when the
+ *     module has delay >= 1 and the stored form (FDG_SAVE_ACTIVATIONS).  The host calls stay serialised, but such a
+ *     module's fdg_forward and fdg_backward_delayed may be given DIFFERENT streams and then overlap on the GPU.  The
+ *     caller orders, with events: fdg_update after that backward (same stream is enough) AND after the forward
+ *     (the forward snapshots the weights the update moves); the next fdg_forward after that update; a
+ *     fdg_backward_delayed after the forward whose context it pops (only an issue at delay-many steps' distance).
+ *     With delay 0, or FDG_SAVE_INPUT_AND_REPLAY, give all calls of a step one stream (or order them fully).
  */
 #ifndef FDG_H_
 #define FDG_H_

@@ -74,7 +74,7 @@ struct Plan {
   // intermediates: inside every slot, or (replay) once per module at o_inter
   size_t s_sums = 0, s_xin = 0, s_acts = 0, s_pooled = 0, s_dl = 0, s_logits = 0;
   size_t o_inter = 0, inter_bytes = 0;
-  size_t o_S[2] = {0, 0}, o_G[2] = {0, 0}, o_GB[2] = {0, 0}, o_T[2] = {0, 0}, o_TP = 0, o_dp = 0;
+  size_t o_S[2] = {0, 0}, o_G[2] = {0, 0}, o_GB[2] = {0, 0}, o_T[2] = {0, 0}, o_TP = 0, o_TPB = 0, o_dp = 0;
   size_t o_wscratch = 0, wscratch_bytes = 0;   // partial sums of the split weight gradient
   size_t total = 0;
 };
@@ -282,6 +282,9 @@ bool build_plan(const fdg_module_desc* desc, int save_mode, Plan& p, fdg_status*
   for (int i = 0; i < 2; ++i) p.o_GB[i] = take(p.maxE * 2);
   for (int i = 0; i < 2; ++i) p.o_T[i] = take(p.maxE * 2);
   p.o_TP = take(std::max(p.maxE, p.is_top ? (size_t)1 + (size_t)N * desc->num_classes : (size_t)0) * 4);
+  // the backward's own copy: a forward and a delayed backward of different contexts share no temporary, so they may
+  // run on two streams at once (delay >= 1, stored form)
+  p.o_TPB = take(desc->delay >= 1 && !p.replay ? p.maxE * 4 : 0);
   p.o_dp = take(p.is_top ? (size_t)N * p.head_C * 4 : 0);
   for (const ConvInfo& ci : p.convs) p.wscratch_bytes = std::max(p.wscratch_bytes, conv_wgrad_scratch_bytes(ci.sh));
   p.o_wscratch = take(p.wscratch_bytes);
@@ -347,6 +350,7 @@ struct fdg_module {
   int64_t seq_fwd = 0, seq_bwd = 0;
   bool has_grad = false;
   hipStream_t last_stream = nullptr;
+  hipStream_t fwd_stream = nullptr;   // the forward's last stream (it may differ from the backward's)
 
   float* params() const { return reinterpret_cast<float*>(ws + p.o_params); }
   float* mom() const { return reinterpret_cast<float*>(ws + p.o_mom); }
@@ -359,6 +363,8 @@ struct fdg_module {
   bf16_t* GB(int i) const { return reinterpret_cast<bf16_t*>(ws + p.o_GB[i]); }
   bf16_t* T(int i) const { return reinterpret_cast<bf16_t*>(ws + p.o_T[i]); }
   float* TP() const { return reinterpret_cast<float*>(ws + p.o_TP); }
+  // projection-shortcut temporary of the backward: its own where forward and backward may overlap
+  float* TPB() const { return reinterpret_cast<float*>(ws + ((p.d.delay >= 1 && !p.replay) ? p.o_TPB : p.o_TP)); }
 };
 
 namespace {
@@ -738,6 +744,7 @@ fdg_status fdg_module_create_ex(const fdg_module_desc* desc, int32_t save_mode, 
   m->ws = static_cast<char*>(dev_workspace);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   m->last_stream = s;
+  m->fwd_stream = s;
   (void)side_create(m->side);   // without it the weight gradients simply stay on the caller's stream
   const Plan& p = m->p;
   // parameters, momentum, gradients, backward sums, running statistics (mean 0, var 1), emit table
@@ -775,7 +782,7 @@ fdg_status fdg_forward(fdg_module* m, const float* x_dev, const int32_t* labels_
   if (p.is_top != (labels_dev != nullptr)) return FDG_ERR_INVALID_ARG;
   if (m->seq_fwd - m->seq_bwd >= p.d.delay + 1) return FDG_ERR_QUEUE_FULL;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  m->last_stream = s;
+  m->fwd_stream = s;
   FDG_TRY(side_join(m, s));
   SlotView v = view_of(m, m->seq_fwd);
   const int N = p.d.n;
@@ -830,8 +837,8 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
                             p.head_C, J, s));
       if (L.kind == FDG_HEAD_PREACT) {
         const BnInfo& b0 = p.bns[L.bn[0]];
-        FDG_TRY(launch_pool_bwd(dp, m->TP(), nullptr, N, p.head_HW, p.head_C, s));
-        FDG_TRY(bn_backward(m, v, b0, m->TP(), true, v.act(L.act[0]), in_b, nullptr, m->G(nxt), m->GB(nxt), s));
+        FDG_TRY(launch_pool_bwd(dp, m->TPB(), nullptr, N, p.head_HW, p.head_C, s));
+        FDG_TRY(bn_backward(m, v, b0, m->TPB(), true, v.act(L.act[0]), in_b, nullptr, m->G(nxt), m->GB(nxt), s));
       } else {
         FDG_TRY(side_wait_readers(m, m->GB(nxt), s));
         FDG_TRY(launch_pool_bwd(dp, m->G(nxt), m->GB(nxt), N, p.head_HW, p.head_C, s));
@@ -859,8 +866,8 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
         FDG_TRY(bn_backward(m, v, bp, m->G(cur), true, t_y, v.act(L.act[3]), nullptr, nullptr, m->T(1), s));
         FDG_TRY(mconv_wgrad(m, cp, in_b, m->T(1), s));
         if (need_dx) {
-          FDG_TRY(mconv_dgrad(m, cp, m->T(1), v.Wt(cp), nullptr, nullptr, m->TP(), nullptr, s));
-          FDG_TRY(mconv_dgrad(m, c1, m->T(0), v.Wt(c1), m->TP(), nullptr, m->G(nxt), m->GB(nxt), s));
+          FDG_TRY(mconv_dgrad(m, cp, m->T(1), v.Wt(cp), nullptr, nullptr, m->TPB(), nullptr, s));
+          FDG_TRY(mconv_dgrad(m, c1, m->T(0), v.Wt(c1), m->TPB(), nullptr, m->G(nxt), m->GB(nxt), s));
         }
       } else if (need_dx) {
         // identity shortcut: the masked incoming gradient joins the branch gradient.  Where the narrow kernel runs
@@ -893,8 +900,8 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
       if (L.projects) {
         const ConvInfo& cp = p.convs[L.conv[2]];
         FDG_TRY(mconv_wgrad(m, cp, t_o1, m->GB(cur), s));
-        FDG_TRY(mconv_dgrad(m, cp, m->GB(cur), v.Wt(cp), nullptr, nullptr, m->TP(), nullptr, s));
-        FDG_TRY(dgrad_relu_bn_backward(m, v, c1, m->T(1), v.Wt(c1), m->TP(), b1, t_o1, in_b, m->T(0), nullptr,
+        FDG_TRY(mconv_dgrad(m, cp, m->GB(cur), v.Wt(cp), nullptr, nullptr, m->TPB(), nullptr, s));
+        FDG_TRY(dgrad_relu_bn_backward(m, v, c1, m->T(1), v.Wt(c1), m->TPB(), b1, t_o1, in_b, m->T(0), nullptr,
                                        need_dx ? m->G(nxt) : nullptr, need_dx ? m->GB(nxt) : nullptr, s));
       } else {
         FDG_TRY(dgrad_relu_bn_backward(m, v, c1, m->T(1), v.Wt(c1), nullptr, b1, t_o1, in_b, m->T(0), m->G(cur),
@@ -960,6 +967,7 @@ fdg_status fdg_set_params(fdg_module* m, const float* host_src, size_t count) {
   std::vector<float> buf(m->p.P, 0.f);
   ext_to_int(m->p, host_src, buf.data());
   FDG_TRY(hipStreamSynchronize(m->last_stream));
+  if (m->fwd_stream != m->last_stream) FDG_TRY(hipStreamSynchronize(m->fwd_stream));
   FDG_TRY(hipMemcpy(m->params(), buf.data(), m->p.P * 4, hipMemcpyHostToDevice));
   FDG_TRY(hipMemset(m->mom(), 0, m->p.P * 4));
   FDG_TRY(hipDeviceSynchronize());
@@ -970,6 +978,7 @@ static fdg_status read_arena(const fdg_module* m, const float* dev, float* host_
   if (!m || !host_dst || count != m->p.ext_params) return FDG_ERR_INVALID_ARG;
   std::vector<float> buf(m->p.P);
   FDG_TRY(hipStreamSynchronize(m->last_stream));
+  if (m->fwd_stream != m->last_stream) FDG_TRY(hipStreamSynchronize(m->fwd_stream));
   FDG_TRY(hipMemcpy(buf.data(), dev, m->p.P * 4, hipMemcpyDeviceToHost));
   int_to_ext(m->p, buf.data(), host_dst);
   return FDG_OK;
@@ -991,6 +1000,7 @@ fdg_status fdg_get_bn_running(const fdg_module* m, float* host_dst, size_t count
   // the arena holds the BNs in creation order; report them in parameter order
   std::vector<float> buf(count);
   FDG_TRY(hipStreamSynchronize(m->last_stream));
+  if (m->fwd_stream != m->last_stream) FDG_TRY(hipStreamSynchronize(m->fwd_stream));
   FDG_TRY(hipMemcpy(buf.data(), m->running(), count * 4, hipMemcpyDeviceToHost));
   size_t o = 0;
   for (const ParamTensor& t : m->p.ptensors) {
@@ -1037,6 +1047,7 @@ fdg_status fdg_queue_state(const fdg_module* m, int32_t* outstanding, int64_t* o
 fdg_status fdg_profile_enable(fdg_module* m, int enable) {
   if (!m) return FDG_ERR_INVALID_ARG;
   FDG_TRY(hipStreamSynchronize(m->last_stream));
+  if (m->fwd_stream != m->last_stream) FDG_TRY(hipStreamSynchronize(m->fwd_stream));
   m->prof.reset();
   m->prof.on = enable != 0;
   return FDG_OK;
@@ -1045,6 +1056,7 @@ fdg_status fdg_profile_enable(fdg_module* m, int enable) {
 fdg_status fdg_profile_read(fdg_module* m, fdg_profile_entry* out, int32_t capacity, int32_t* count) {
   if (!m || !count || (capacity > 0 && !out)) return FDG_ERR_INVALID_ARG;
   FDG_TRY(hipStreamSynchronize(m->last_stream));
+  if (m->fwd_stream != m->last_stream) FDG_TRY(hipStreamSynchronize(m->fwd_stream));
   // one entry per (class, kernel and layer shape)
   std::vector<fdg_profile_entry> acc;
   for (const ProfRecord& r : m->prof.recs) {

@@ -105,3 +105,55 @@ def test_replay_workspace_is_smaller():
     assert b.workspace_bytes < a.workspace_bytes
     a.close()
     b.close()
+
+
+@pytest.mark.parametrize("name", ["postact_identity_delay1", "bottom_stack_delay2"])
+def test_forward_and_delayed_backward_on_two_streams(name):
+    """include/fdg.h, "Two streams": with delay >= 1 the forward (newest context) and the delayed backward (oldest
+    context) share no temporary and may overlap on the GPU; the caller orders the update after both and the next
+    forward after the update.  Same iteration as on one stream, up to the order of atomic sums; the weights are frozen
+    (lr = 0) because two runs whose weights move round them to bf16 independently after the first update and then differ
+    by per cents whatever the streams (the envelope of tests/gpu_harness.py exists for that)."""
+    import torch
+    from paper_1906_09108_amd import FdgModule
+    spec = copy.deepcopy({**STRICT, **ENVELOPE}[name])
+    print(f"two streams {name}", flush=True)
+    theta = W.make_params(spec, 6, perturb_bn=True)
+    d = spec.delay
+    runs = []
+    for two in (False, True):
+        m = FdgModule(spec)
+        m.set_params(theta)
+        grad_in = None if spec.is_bottom else torch.empty(spec.input_shape(), dtype=torch.float32, device="cuda")
+        s_f, s_b = (torch.cuda.Stream(), torch.cuda.Stream()) if two else (torch.cuda.current_stream(),) * 2
+        ev_f, ev_u = torch.cuda.Event(), torch.cuda.Event()
+        torch.cuda.synchronize()
+        ev_u.record(s_b)
+        got = []
+        ys = []
+        for t in range(d + 3):
+            x = torch.from_numpy(W.make_input(spec, t, 6)).cuda()
+            torch.cuda.synchronize()                       # x is ready for whichever stream reads it
+            s_f.wait_event(ev_u)
+            ys.append(m.forward(x, None, stream=s_f))
+            ev_f.record(s_f)
+            if t >= d:
+                g = torch.from_numpy(W.make_grad_out(spec, t - d, 6)).cuda(non_blocking=False)
+                m.backward_delayed(g, grad_in, stream=s_b)
+                s_b.wait_event(ev_f)
+                m.update(0.0, stream=s_b)
+                ev_u.record(s_b)
+                torch.cuda.synchronize()
+                got.append(("grads", m.get_grads()))
+                if grad_in is not None:
+                    got.append(("grad_in", grad_in.cpu().numpy()))
+            torch.cuda.synchronize()                       # the forward's stream is not the one the copy below runs on
+            got.append(("y", ys[-1].cpu().numpy()))
+        got.append(("theta", m.get_params()))
+        got.append(("running", m.get_bn_running()))
+        m.close()
+        runs.append(got)
+    for (k, a), (_, b) in zip(*runs):
+        assert np.abs(a).max() > 0, k
+        assert rel_l2(b, a) <= 2.0 ** -8 and rel_err(b, a) <= TOL, (k, rel_l2(b, a), rel_err(b, a))
+
