@@ -86,6 +86,11 @@ CONV_CASES = [  # n, h, w, ci, co, ksize, stride
     (40, 16, 16, 32, 32, 3, 1),
     (64, 16, 16, 32, 32, 3, 1),
     (9, 64, 64, 64, 64, 3, 1),
+    # degenerate images: one pixel, one row, one column (every tap but the centre falls outside)
+    (1, 1, 1, 16, 16, 3, 1),
+    (2, 1, 7, 32, 32, 3, 1),
+    (2, 7, 1, 16, 16, 3, 1),
+    (3, 2, 2, 64, 64, 3, 1),
 ]
 
 
