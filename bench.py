@@ -40,6 +40,8 @@ def parse_args():
     ap.add_argument("--two-streams", action="store_true",
                     help="forward on one stream, delayed backward + update on another (modules with delay >= 1: the two touch "
                          "different saved forwards and overlap on the GPU)")
+    ap.add_argument("--graph", action="store_true",
+                    help="record the step into HIP graphs (one per position of the history ring) and time their replay")
     ap.add_argument("--replay", action="store_true",
                     help="FDG_SAVE_INPUT_AND_REPLAY: a saved forward is its input and weight snapshot; the backward runs the forward again")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -159,6 +161,9 @@ def main():
     if two and (spec.delay < 1 or args.replay):
         print("--two-streams needs a module with delay >= 1 in the stored form", file=sys.stderr)
         sys.exit(2)
+    if two and args.graph:
+        print("--graph records a step on one stream; it is not combined with --two-streams", file=sys.stderr)
+        sys.exit(2)
     if two:
         s_fwd, s_bwd = torch.cuda.Stream(), torch.cuda.Stream()
         ev_fwd, ev_upd = torch.cuda.Event(), torch.cuda.Event()
@@ -182,6 +187,29 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+    eager_step = step
+    if args.graph:
+        # One graph per ring position (the slot pointers of a step are fixed in it); the replays continue the cycle
+        # the recording went through.  The library allocates nothing, clears memory with kernels (no memset nodes)
+        # and forks / joins its own second stream with events, so a whole step records as it is.
+        period = spec.delay + 1
+        s_main = torch.cuda.Stream()
+        graphs = []
+        for ph in range(period):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=s_main):
+                i = args.warmup + ph
+                mod.forward(xs[i % pool], labels[i % pool], y, s_main)
+                mod.backward_delayed(gs[i % pool], grad_in, s_main)
+                mod.update(lr, s_main)
+            graphs.append(g)
+        torch.cuda.synchronize()
+
+        def step(i):   # noqa: F811 -- from here on a step is a replay
+            graphs[(i - args.warmup) % period].replay()
+        for i in range(args.warmup, args.warmup + period):
+            step(i)
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(args.warmup + i)
@@ -193,7 +221,10 @@ def main():
         print("non-finite module output", file=sys.stderr)
         sys.exit(1)
 
-    # second pass over the same number of steps with per-class HIP events
+    # second pass over the same number of steps with per-class HIP events (eager: the profiler's events are not
+    # part of a recorded graph)
+    step = eager_step
+    torch.cuda.synchronize()
     mod.profile_enable(True)
     for i in range(args.steps):
         step(args.warmup + args.steps + i)
@@ -246,6 +277,7 @@ def main():
         "config": {"workload": spec.name, "batch": spec.n, "delay": spec.delay, "beta": spec.beta,
                    "saved_forward": "input + weight snapshot, replayed by the backward" if args.replay else "activations",
                    "streams": "forward on one, delayed backward + update on another" if args.two_streams else "one",
+                   "launch": "HIP graph replay" if args.graph else "eager",
                    "workspace_MiB": mod.workspace_bytes / 2 ** 20,
                    "params": W.param_count(spec), "useful_conv_gflop_per_step": W.conv_flops(spec) / 1e9},
         "step_tflops": W.conv_flops(spec) / (ms_per_step * 1e-3) / 1e12,
