@@ -370,9 +370,13 @@ __device__ __forceinline__ bf16x8 narrow_join(NarrowFrag& f) {
   return __builtin_bit_cast(bf16x8, both);
 }
 
-template <int C>
+// STEM: x has 8 channels in memory (3 real ones, the stem of a network); in LDS a position of x is 16 channels wide with
+// the upper 8 zero, so that the same transposing reads apply, and only the real input channels are stored.
+template <int C, bool STEM>
 __global__ __launch_bounds__(256) void conv_wgrad_narrow_kernel(WgradArgs a, NarrowWgradLaunch L) {
   constexpr int U = C / 8, ROWB = C * 2, NCB = C / 16, WK = 4 / NCB;
+  constexpr int UX = STEM ? 2 : U, ROWBX = UX * 16, NCBI = STEM ? 1 : NCB;   // x side: units, bytes, 16-channel blocks
+  constexpr bool SWZ_DY = C == 64, SWZ_X = !STEM && C == 64;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -384,27 +388,31 @@ __global__ __launch_bounds__(256) void conv_wgrad_narrow_kernel(WgradArgs a, Nar
   // dy region: idx 0 is the first position of padded row pr0.  With 64 channels the 32-byte slot of a position is
   // XORed with bit 1 of idx (the four pixels of a transposing read then fall into four bank groups).
   int pr0 = 0;                                       // first padded row (over all images) of the current tile
-  auto fill = [&](const bf16_t* src, int units, int lead, int first_row, int nrows, int lds_unit0) {
+  // ulog: log2 of the units per position in LDS; src_units: units per pixel that exist in memory (the others are
+  // zeros); pitch: channels per pixel in memory
+  auto fill = [&](const bf16_t* src, int units, int lead, int first_row, int nrows, int lds_unit0, int ulog, int src_units,
+                  int pitch, bool swz) {
     for (int base = wave * 64; base < units; base += 256) {
       const int pos = base + lane;
-      const int idx = pos / U, us = pos % U;
-      const int u = C == 64 ? (us ^ ((idx & 2) << 1)) : us;
+      const int idx = pos >> ulog, us = pos & ((1 << ulog) - 1);
+      const int u = swz ? (us ^ ((idx & 2) << 1)) : us;
       const int xp = idx - lead;
       const int lr = xp >= 0 ? xp / PW : -1;
       const int c = xp - lr * PW;
       const int gr = first_row + lr;
       const int n = gr >= 0 ? gr / HP : 0;
       const int hr = gr - n * HP;
-      const bool ok = lr >= 0 && lr < nrows && gr >= 0 && gr < L.rows_total && hr >= 1 && hr <= H && c >= 1 && c <= W;
-      const char* g = reinterpret_cast<const char*>(src + (((size_t)n * H + (hr - 1)) * W + (c - 1)) * C + u * 8);
+      const bool ok = u < src_units && lr >= 0 && lr < nrows && gr >= 0 && gr < L.rows_total && hr >= 1 && hr <= H && c >= 1 && c <= W;
+      const char* g = reinterpret_cast<const char*>(src + (((size_t)n * H + (hr - 1)) * W + (c - 1)) * pitch + u * 8);
       narrow_dma16(ok ? g : zero, smem + (size_t)(lds_unit0 + base) * 16);
     }
   };
-  f32x4 acc[9][NCB];
+  constexpr int ULOG = U == 2 ? 1 : (U == 4 ? 2 : 3), UXLOG = UX == 2 ? 1 : (UX == 4 ? 2 : 3);
+  f32x4 acc[9][NCBI];
 #pragma unroll
   for (int t = 0; t < 9; ++t)
 #pragma unroll
-    for (int j = 0; j < NCB; ++j) acc[t][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < NCBI; ++j) acc[t][j] = f32x4{0.f, 0.f, 0.f, 0.f};
   int shift[9];   // x idx of a tap relative to the dy position
 #pragma unroll
   for (int t = 0; t < 9; ++t) {
@@ -414,31 +422,31 @@ __global__ __launch_bounds__(256) void conv_wgrad_narrow_kernel(WgradArgs a, Nar
 
   const int g = lane >> 4, i16 = lane & 15;
   const unsigned dy0 = (unsigned)L.xunits * 16u;
-  constexpr int TB = C == 16 ? 9 : 3;                // taps whose fragments are read in one batch
+  constexpr int TB = NCBI == 1 ? 9 : 3;              // taps whose fragments are read in one batch
   const int first_tile = narrow_xcd_consecutive(blockIdx.x, gridDim.x);
   for (int tile = first_tile; tile < L.tiles; tile += gridDim.x) {
     if (tile != first_tile) __syncthreads();           // every wave is done reading the previous tile
     pr0 = tile * L.R;
-    fill(a.x, L.xunits, 1, pr0 - 1, L.R + 2, 0);
-    fill(a.dy, L.dyunits, 0, pr0, L.R, L.xunits);
+    fill(a.x, L.xunits, 1, pr0 - 1, L.R + 2, 0, UXLOG, STEM ? 1 : UX, STEM ? 8 : C, SWZ_X);
+    fill(a.dy, L.dyunits, 0, pr0, L.R, L.xunits, ULOG, U, C, SWZ_DY);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     for (int st = wk; st < L.KP / 32; st += WK) {
       const int pp = st * 32 + 4 * g + (i16 >> 2);     // this lane's first pixel position of the step
-      const int aslot = C == 64 ? (wcb ^ (pp & 2)) : wcb;
+      const int aslot = SWZ_DY ? (wcb ^ (pp & 2)) : wcb;
       NarrowFrag ra;
       narrow_read_tr8(ra, dy0 + (unsigned)(pp * ROWB + aslot * 32 + (i16 & 3) * 8), 16 * ROWB);
       bf16x8 fa;
 #pragma unroll
       for (int t0 = 0; t0 < 9; t0 += TB) {
-        NarrowFrag rb[TB][NCB];
+        NarrowFrag rb[TB][NCBI];
 #pragma unroll
         for (int t = 0; t < TB; ++t) {
           const int idx = pp + shift[t0 + t];
 #pragma unroll
-          for (int j = 0; j < NCB; ++j) {
-            const int bslot = C == 64 ? (j ^ (idx & 2)) : j;
-            narrow_read_tr8(rb[t][j], (unsigned)(idx * ROWB + bslot * 32 + (i16 & 3) * 8), 16 * ROWB);
+          for (int j = 0; j < NCBI; ++j) {
+            const int bslot = SWZ_X ? (j ^ (idx & 2)) : j;
+            narrow_read_tr8(rb[t][j], (unsigned)(idx * ROWBX + bslot * 32 + (i16 & 3) * 8), 16 * ROWBX);
           }
         }
         narrow_frags_landed();
@@ -446,7 +454,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_narrow_kernel(WgradArgs a, Nar
 #pragma unroll
         for (int t = 0; t < TB; ++t)
 #pragma unroll
-          for (int j = 0; j < NCB; ++j) acc[t0 + t][j] = mfma16(fa, narrow_join(rb[t][j]), acc[t0 + t][j]);
+          for (int j = 0; j < NCBI; ++j) acc[t0 + t][j] = mfma16(fa, narrow_join(rb[t][j]), acc[t0 + t][j]);
       }
     }
   }
@@ -459,8 +467,8 @@ __global__ __launch_bounds__(256) void conv_wgrad_narrow_kernel(WgradArgs a, Nar
 #pragma unroll
       for (int t = 0; t < 9; ++t)
 #pragma unroll
-        for (int j = 0; j < NCB; ++j)
-          red[(((wk - 1) * NCB + wcb) * 9 * NCB + t * NCB + j) * 64 + lane] = make_float4(acc[t][j][0], acc[t][j][1], acc[t][j][2], acc[t][j][3]);
+        for (int j = 0; j < NCBI; ++j)
+          red[(((wk - 1) * NCB + wcb) * 9 * NCBI + t * NCBI + j) * 64 + lane] = make_float4(acc[t][j][0], acc[t][j][1], acc[t][j][2], acc[t][j][3]);
     }
     __syncthreads();
     if (wk == 0) {
@@ -468,8 +476,8 @@ __global__ __launch_bounds__(256) void conv_wgrad_narrow_kernel(WgradArgs a, Nar
 #pragma unroll
         for (int t = 0; t < 9; ++t)
 #pragma unroll
-          for (int j = 0; j < NCB; ++j) {
-            const float4 v = red[(((o - 1) * NCB + wcb) * 9 * NCB + t * NCB + j) * 64 + lane];
+          for (int j = 0; j < NCBI; ++j) {
+            const float4 v = red[(((o - 1) * NCB + wcb) * 9 * NCBI + t * NCBI + j) * 64 + lane];
             acc[t][j][0] += v.x; acc[t][j][1] += v.y; acc[t][j][2] += v.z; acc[t][j][3] += v.w;
           }
     }
@@ -479,11 +487,11 @@ __global__ __launch_bounds__(256) void conv_wgrad_narrow_kernel(WgradArgs a, Nar
 #pragma unroll
     for (int t = 0; t < 9; ++t) {
 #pragma unroll
-      for (int j = 0; j < NCB; ++j)
+      for (int j = 0; j < NCBI; ++j)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const int co = wcb * 16 + 4 * g + v, ci = j * 16 + i16;
-          out[((size_t)co * 9 + t) * C + ci] = acc[t][j][v];
+          if (ci < a.Ci) out[((size_t)co * 9 + t) * a.Ci + ci] = acc[t][j][v];
         }
     }
   }
@@ -517,8 +525,11 @@ __global__ __launch_bounds__(256) void wgrad_slices_reduce_kernel(float4* __rest
 struct NarrowWgradPlan { NarrowWgradLaunch L; int blocks; size_t lds; };
 
 // tile height: about one tile per compute unit, within 96 KB of LDS; at most 256 workgroups (and slices)
+static bool wgrad_narrow_is_stem(const WgradArgs& a) { return a.Cx == 8 && a.Ci <= 8 && a.Co != a.Cx; }
+
 bool plan_wgrad_narrow(const WgradArgs& a, NarrowWgradPlan& P) {
   const int C = a.Co, U = C / 8, ROWB = C * 2;
+  const int UX = wgrad_narrow_is_stem(a) ? 2 : U, NCBI = wgrad_narrow_is_stem(a) ? 1 : C / 16;
   const int PW = a.Wi + 2, HP = a.Hi + 2;
   const long long rows_total = (long long)a.N * HP;
   if (rows_total * PW >= (1ll << 30)) return false;
@@ -526,9 +537,9 @@ bool plan_wgrad_narrow(const WgradArgs& a, NarrowWgradPlan& P) {
   if (R < 1) R = 1;
   for (;; --R) {
     const int KP = (R * PW + 31) / 32 * 32;
-    const int xpos = KP + 2 * PW + 2, xunits = (xpos * U + 255) / 256 * 256, dyunits = (KP * U + 255) / 256 * 256;
+    const int xpos = KP + 2 * PW + 2, xunits = (xpos * UX + 255) / 256 * 256, dyunits = (KP * U + 255) / 256 * 256;
     const size_t tiles = (size_t)(xunits + dyunits) * 16;
-    const size_t red = C == 64 ? 0 : (size_t)3 * 9 * (C / 16) * 1024;   // blocks of the waves that are added
+    const size_t red = C == 64 ? 0 : (size_t)3 * 9 * NCBI * 1024;   // blocks of the waves that are added
     if (tiles <= 96 * 1024 || R == 1) {
       if (tiles > 96 * 1024) return false;
       P.L.R = R; P.L.PW = PW; P.L.HP = HP; P.L.rows_total = (int)rows_total; P.L.KP = KP;
@@ -573,7 +584,9 @@ bool conv_wgrad_narrow_applies(const WgradArgs& a) {
   static const bool off = getenv("FDG_NO_NARROW") != nullptr || getenv("FDG_NO_NARROW_WGRAD") != nullptr;   // A/B switch for measurements
   if (off) return false;
   if (a.Co != 16 && a.Co != 32 && a.Co != 64) return false;
-  if (a.Ci != a.Co || a.Cx != a.Co || a.ntaps != 9 || a.stride != 1 || a.OH != a.Hi || a.OW != a.Wi) return false;
+  const bool same = a.Ci == a.Co && a.Cx == a.Co;                  // C -> C
+  if (!same && !wgrad_narrow_is_stem(a)) return false;              // or the stem: 3 (stored as 8) -> C
+  if (a.Ci < 1 || a.ntaps != 9 || a.stride != 1 || a.OH != a.Hi || a.OW != a.Wi) return false;
   for (int i = 0; i < 9; ++i) {
     const int dh = (a.tap[i] & 0xff) - 8, dw = ((a.tap[i] >> 8) & 0xff) - 8;
     if (dh < -1 || dh > 1 || dw < -1 || dw > 1) return false;
@@ -588,19 +601,19 @@ size_t conv_wgrad_narrow_scratch_bytes(const WgradArgs& a) {
   return (size_t)P.blocks * a.Co * 9 * a.Ci * 4;
 }
 
-template <int C>
+template <int C, bool STEM>
 static hipError_t run_wgrad_narrow(const WgradArgs& a, const NarrowWgradPlan& P, hipStream_t s) {
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad_narrow_kernel<C>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad_narrow_kernel<C, STEM>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
     if (e != hipSuccess) return e;
     configured = true;
   }
   static char name[64];
-  if (!name[0]) snprintf(name, sizeof(name), "conv_wgrad_narrow_kernel<%d>", C);
+  if (!name[0]) snprintf(name, sizeof(name), STEM ? "conv_wgrad_narrow_kernel<%d, stem>" : "conv_wgrad_narrow_kernel<%d>", C);
   note_kernel(name);
-  hipLaunchKernelGGL((conv_wgrad_narrow_kernel<C>), dim3(P.blocks), dim3(256), P.lds, s, a, P.L);
+  hipLaunchKernelGGL((conv_wgrad_narrow_kernel<C, STEM>), dim3(P.blocks), dim3(256), P.lds, s, a, P.L);
   return hipGetLastError();
 }
 
@@ -611,7 +624,11 @@ hipError_t launch_conv_wgrad_narrow(const WgradArgs& a, hipStream_t s) {
   if (!a.scratch || a.scratch_bytes < (size_t)P.blocks * n * 4) return hipErrorInvalidValue;
   P.L.partial = a.scratch;
   P.L.stride = n;
-  hipError_t e = a.Co == 16 ? run_wgrad_narrow<16>(a, P, s) : (a.Co == 32 ? run_wgrad_narrow<32>(a, P, s) : run_wgrad_narrow<64>(a, P, s));
+  hipError_t e;
+  if (wgrad_narrow_is_stem(a))
+    e = a.Co == 16 ? run_wgrad_narrow<16, true>(a, P, s) : (a.Co == 32 ? run_wgrad_narrow<32, true>(a, P, s) : run_wgrad_narrow<64, true>(a, P, s));
+  else
+    e = a.Co == 16 ? run_wgrad_narrow<16, false>(a, P, s) : (a.Co == 32 ? run_wgrad_narrow<32, false>(a, P, s) : run_wgrad_narrow<64, false>(a, P, s));
   if (e != hipSuccess) return e;
   const int n4 = (int)(n / 4);
   hipLaunchKernelGGL(wgrad_slices_reduce_kernel, dim3((n4 + 15) / 16), dim3(256), 0, s, reinterpret_cast<float4*>(a.dw),

@@ -86,6 +86,10 @@ CONV_CASES = [  # n, h, w, ci, co, ksize, stride
     (40, 16, 16, 32, 32, 3, 1),
     (64, 16, 16, 32, 32, 3, 1),
     (9, 64, 64, 64, 64, 3, 1),
+    # stems: 3 input channels (stored as 8) into a narrow layer
+    (8, 32, 32, 3, 16, 3, 1),
+    (2, 64, 64, 3, 64, 3, 1),
+    (3, 9, 7, 3, 32, 3, 1),
     # degenerate images: one pixel, one row, one column (every tap but the centre falls outside)
     (1, 1, 1, 16, 16, 3, 1),
     (2, 1, 7, 32, 32, 3, 1),
