@@ -1,5 +1,5 @@
-// Convolutions of the narrow layers (16, 32 or 64 channels in and out, 3x3, unit stride): the ResNet-56 / -110 /
-// -1202 stages and the first stage of ResNet-18.  Such a layer moves a few megabytes and does a few hundred
+// Convolutions of the narrow layers (16, 32 or 64 channels in and out, or the stem's 3 -- stored as 8 -- into 16 / 32 /
+// 64; 3x3, unit stride): the ResNet-56 / -110 / -1202 stages and the first stage of ResNet-18.  Such a layer moves a few megabytes and does a few hundred
 // megaflops per launch, so what a launch costs is the length of the dependent chain inside one workgroup, not the
 // arithmetic: the generic kernel walks the contraction in 32-wide chunks, each chunk a round trip global memory ->
 // registers -> LDS -> barrier, and a filter tap at a time re-reads the pixels nine times.  Here a workgroup
@@ -174,7 +174,7 @@ __global__ __launch_bounds__(256) void conv_narrow_kernel(GatherConvArgs a, Narr
   constexpr int WM = 4 / WN, TP = 16 * J * WM, CO = 16 * NB * WN;
   constexpr int U = CI / 8, ROWB = CI * 2;          // 16-byte units and bytes of one pixel
   constexpr int S = (9 * CI + 31) / 32;             // 32-wide steps of the contraction (taps x channels)
-  constexpr int SWZ_SHIFT = U == 2 ? 2 : (U == 4 ? 1 : 0);   // unit index ^= (row >> SWZ_SHIFT) & (U - 1): b128 reads of 8 consecutive rows hit 8 bank groups
+  constexpr int SWZ_SHIFT = U == 2 ? 2 : (U == 4 ? 1 : 0);   // (U == 1, the 8-channel stem input: nothing to swizzle)   // unit index ^= (row >> SWZ_SHIFT) & (U - 1): b128 reads of 8 consecutive rows hit 8 bank groups
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -248,8 +248,8 @@ __global__ __launch_bounds__(256) void conv_narrow_kernel(GatherConvArgs a, Narr
 #pragma unroll
         for (int s = 0; s < SA; ++s) {
           // which tap and which unit of the pixel this lane's 8 k values are
-          const int slot = CI == 16 ? 2 * s + (g >> 1) : s;
-          const int u = CI == 16 ? (g & 1) : g;
+          const int slot = CI == 8 ? 4 * s + g : (CI == 16 ? 2 * s + (g >> 1) : s);
+          const int u = CI == 8 ? 0 : (CI == 16 ? (g & 1) : g);
           unsigned addr = zero_addr;
           if (slot < 9) {
             const int tp = a.tap[slot];
@@ -558,8 +558,9 @@ bool plan_wgrad_narrow(const WgradArgs& a, NarrowWgradPlan& P) {
 bool conv_narrow_applies(const GatherConvArgs& a) {
   static const bool off = getenv("FDG_NO_NARROW") != nullptr || getenv("FDG_NO_NARROW_CONV") != nullptr;   // A/B switch for measurements
   if (off) return false;
-  if (a.Ci != 16 && a.Ci != 32 && a.Ci != 64) return false;
-  if (a.Co != a.Ci || a.w_rows != a.Co || a.Kw != 9 * a.Ci) return false;
+  const bool stem = a.Ci == 8 && (a.Co == 16 || a.Co == 32 || a.Co == 64);   // 3 input channels stored as 8
+  if (!stem && a.Ci != 16 && a.Ci != 32 && a.Ci != 64) return false;
+  if ((!stem && a.Co != a.Ci) || a.w_rows != a.Co || a.Kw != 9 * a.Ci) return false;
   if (a.ntaps != 9 || a.in_stride != 1 || a.out_stride != 1 || a.ooh != 0 || a.oow != 0 || a.nclass > 1) return false;
   if (a.OH != a.Hi || a.OW != a.Wi || a.OHf != a.OH || a.OWf != a.OW || a.Wi < 1 || a.Wi > 1024 || a.Hi > 1024) return false;
   if ((long long)a.N * a.Hi * a.Wi >= (1ll << 30)) return false;
@@ -575,6 +576,7 @@ bool conv_narrow_applies(const GatherConvArgs& a) {
 
 hipError_t launch_conv_narrow(const GatherConvArgs& a, hipStream_t s) {
   if (!conv_narrow_applies(a) || a.N * a.OH * a.OW <= 0) return hipErrorInvalidValue;
+  if (a.Ci == 8) return a.Co == 16 ? run_narrow_j<8, 1, 1>(a, s) : (a.Co == 32 ? run_narrow_j<8, 2, 1>(a, s) : run_narrow_j<8, 4, 1>(a, s));
   if (a.Ci == 16) return run_narrow_j<16, 1, 1>(a, s);
   if (a.Ci == 32) return run_narrow_j<32, 2, 1>(a, s);
   return run_narrow_j<64, 2, 2>(a, s);
