@@ -1,5 +1,6 @@
-"""The convolution and batch-norm kernels at the benchmark's full sizes (configuration 4, batch 128), in
-the launch configuration bench.py times, checked on sub-problems the oracle computes exactly:
+"""The convolution and batch-norm kernels at the benchmarks' full sizes (batch 128: the layers of configuration 4,
+and the narrow layers and stems of configurations 2, 3, 5 and 7), in the launch configuration bench.py times,
+checked on sub-problems the oracle computes exactly:
 
   * forward and data gradient are independent per image, so the oracle runs on a few images of the batch
     and those images' outputs are compared element by element;
@@ -27,6 +28,12 @@ FULL_CASES = [
     (128, 16, 16, 320, 320, 3, 1),
     (128, 16, 16, 320, 640, 3, 2),
     (128, 16, 16, 320, 640, 1, 2),
+    # narrow layers (ResNet-110 / ResNet-56 stages, the 64-channel stage at 64x64) and the stems (3 channels stored as 8)
+    (128, 32, 32, 16, 16, 3, 1),
+    (128, 16, 16, 32, 32, 3, 1),
+    (128, 64, 64, 64, 64, 3, 1),
+    (128, 32, 32, 3, 16, 3, 1),
+    (128, 64, 64, 3, 64, 3, 1),
 ]
 IMAGES = [0, 63, 127]
 
@@ -39,6 +46,17 @@ def _t():
 def rel(got, ref):
     d = np.abs(ref).max()
     return float(np.abs(np.asarray(got, np.float64) - ref).max() / (d if d > 0 else 1.0))
+
+
+def _sel(c, wanted):
+    """The indices of `wanted` that exist among c channels (negative ones count from the end)."""
+    return sorted({i % c for i in wanted if -c <= i < c})
+
+
+def _pad_last(dev, to):
+    """A device tensor with its last dimension zero-filled up to `to` (input channels are stored in eights)."""
+    t = _t()
+    return dev if dev.shape[-1] == to else t.nn.functional.pad(dev, (0, to - dev.shape[-1])).contiguous()
 
 
 def _dev_bf16(shape, seed, scale=1.0):
@@ -57,8 +75,10 @@ def test_conv_forward_and_data_gradient_on_sampled_images(case):
     print("full-size conv fwd/dgrad", case, flush=True)
     pad = 1 if k == 3 else 0
     ho, wo = (h - 1) // s + 1, (w - 1) // s + 1
+    cip = (ci + 7) // 8 * 8
     xd, x = _dev_bf16((n, h, w, ci), 1)                               # NHWC
     wd, wt = _dev_bf16((co, k * k, ci), 2, (2.0 / (ci * k * k)) ** 0.5)  # [co][tap][ci]
+    xd, wd = _pad_last(xd, cip), _pad_last(wd, cip)
     w_oihw = wt.reshape(co, k, k, ci).transpose(0, 3, 1, 2).copy()
     y16 = t.zeros((n, ho, wo, co), dtype=t.bfloat16, device="cuda")
     y32 = t.full((n, ho, wo, co), float("nan"), dtype=t.float32, device="cuda")
@@ -80,14 +100,15 @@ def test_conv_forward_and_data_gradient_on_sampled_images(case):
     # data gradient with the same weights stored [ci][tap][co]
     dyd, dy = _dev_bf16((n, ho, wo, co), 3)
     wtd = wd.permute(2, 1, 0).contiguous()
-    dx32 = t.full((n, h, w, ci), float("nan"), dtype=t.float32, device="cuda")
-    dx16 = t.zeros((n, h, w, ci), dtype=t.bfloat16, device="cuda")
+    dx32 = t.full((n, h, w, cip), float("nan"), dtype=t.float32, device="cuda")
+    dx16 = t.zeros((n, h, w, cip), dtype=t.bfloat16, device="cuda")
     K.fdgk_conv_dgrad(dyd, wtd, None, None, dx32, dx16, n, h, w, ci, co, k, s)
     t.cuda.synchronize()
     dy_sel = dy[IMAGES].transpose(0, 3, 1, 2).copy()
     dref = K32.conv_bwd_data(dy_sel, w_oihw, (len(IMAGES), ci, h, w), s, pad).astype(np.float64)
-    assert rel(dx32[IMAGES].cpu().numpy().transpose(0, 3, 1, 2), dref) <= F32_TOL
-    assert rel(dx16[IMAGES].to(t.float32).cpu().numpy().transpose(0, 3, 1, 2), dref) <= B16_TOL
+    assert rel(dx32[IMAGES][..., :ci].cpu().numpy().transpose(0, 3, 1, 2), dref) <= F32_TOL
+    assert rel(dx16[IMAGES][..., :ci].to(t.float32).cpu().numpy().transpose(0, 3, 1, 2), dref) <= B16_TOL
+    assert bool((dx32[..., ci:] == 0).all())
     assert bool(t.isfinite(dx32).all())
 
 
@@ -101,29 +122,31 @@ def test_conv_weight_gradient_on_sampled_channels(case):
     ho, wo = (h - 1) // s + 1, (w - 1) // s + 1
     xd, x = _dev_bf16((n, h, w, ci), 5)
     dyd, dy = _dev_bf16((n, ho, wo, co), 6)
-    co_sel = [0, 31, 32, 127, 128, co // 2 + 1, co - 33, co - 1]      # across MFMA blocks, tiles and both ends
-    ci_sel = [0, 15, 16, 63, 64, ci // 2 - 1, ci - 65, ci - 1]
+    cip = (ci + 7) // 8 * 8
+    co_sel = _sel(co, [0, 15, 16, 31, 32, 127, 128, co // 2 + 1, -33, -1])   # across MFMA blocks, tiles and both ends
+    ci_sel = _sel(ci, [0, 2, 15, 16, 63, 64, ci // 2 - 1, -65, -1])
     x_sel = x[..., ci_sel].transpose(0, 3, 1, 2).copy()
     dy_sel = dy[..., co_sel].transpose(0, 3, 1, 2).copy()
-    ref = K32.conv_bwd_weight(x_sel, dy_sel, k, s, pad).astype(np.float64)   # [8, 8, k, k]
+    ref = K32.conv_bwd_weight(x_sel, dy_sel, k, s, pad).astype(np.float64)   # [len(co_sel), len(ci_sel), k, k]
+    xd = _pad_last(xd, cip)
     nbytes = K.fdgk_conv_wgrad_scratch_bytes(n, h, w, ci, co, k, s)
     scratch = t.full((max(nbytes // 4, 4),), float("nan"), dtype=t.float32, device="cuda")
-    dw = t.full((co, k * k, ci), 7.0, dtype=t.float32, device="cuda")
+    dw = t.full((co, k * k, ci), 7.0, dtype=t.float32, device="cuda")   # unpadded: [co][tap][ci]
     K.fdgk_conv_wgrad(xd, dyd, dw, scratch if nbytes else None, n, h, w, ci, co, k, s, overwrite=True)
     t.cuda.synchronize()
     assert bool(t.isfinite(dw).all())
     got = dw.cpu().numpy().reshape(co, k, k, ci)[co_sel][:, :, :, ci_sel].transpose(0, 3, 1, 2)
-    # fp32 accumulation over up to 32768 pixel products of unit-variance operands
+    # fp32 accumulation over up to 524288 pixel products of unit-variance operands
     assert rel(got, ref) <= F32_TOL
 
 
-@pytest.mark.parametrize("m,c", [(128 * 8 * 8, 640), (128 * 16 * 16, 320)])
+@pytest.mark.parametrize("m,c", [(128 * 8 * 8, 640), (128 * 16 * 16, 320), (128 * 32 * 32, 16), (128 * 64 * 64, 64)])
 def test_batch_norm_on_sampled_channels(m, c):
     from paper_1906_09108_amd import kernels as K
     t = _t()
     print("full-size bn", m, c, flush=True)
     eps = 1e-5
-    sel = [0, 7, 8, c // 2, c - 9, c - 1]
+    sel = _sel(c, [0, 7, 8, c // 2, -9, -1])
     r = np.random.default_rng(m + c)
     xd, x = _dev_bf16((m, c), 11, 1.5)
     gamma = (1 + 0.2 * r.standard_normal(c)).astype(np.float32)
