@@ -521,15 +521,17 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(GatherConvArgs a, int m
 // first by bit 5 of every fragment address.  Weight stages are BN rows: with 64 rows per load instruction of the
 // workgroup BN = 160 needs 2.5 of them, so the third load of waves 4 .. 7 goes to a dump area (every wave then counts
 // the same number of loads).
-template <int BN, int PR, int WS>
+template <int BN, int PR, int WS, bool KTAIL>
 __global__ __launch_bounds__(512) void conv_patch256_kernel(GatherConvArgs a, int m_tiles, int n_tiles) {
   constexpr int BM = 256, ROWB = 128, NWAVES = 8;
   static_assert(BN % 32 == 0 && PR % 64 == 0, "whole DMA instructions and 32x32 blocks");
   constexpr int JX = PR / 64, JW = (BN + 63) / 64;
   constexpr int FM = 2, FN = BN / 32;
   constexpr int XBYTES = PR * ROWB + 256, WBYTES = BN * ROWB;   // a patch buffer ends with two rows of zeros
-  constexpr int DUMP = 2 * XBYTES + WS * WBYTES;                // 4 KB that nobody reads
-  constexpr int LDS_BYTES = DUMP + 4096;
+  constexpr int DUMP = 2 * XBYTES + WS * WBYTES;                // 1 KB per wave_m that nobody reads, or one for all
+  constexpr int DUMP_EACH = DUMP + 4096 <= 160 * 1024 ? 1024 : 0;
+  constexpr int LDS_BYTES = DUMP + (DUMP_EACH ? 4096 : 1024);
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS of one compute unit");
   static_assert((WS - 2) * JW + JX < 64, "vmcnt range");
   static_assert(WS >= 3 && WS <= 7, "pipeline depth");
   static_assert((size_t)LDS_BYTES >= (size_t)4 * FN * 4096 && (size_t)LDS_BYTES >= (size_t)8 * out_stage16_bytes(BN) &&
@@ -572,24 +574,62 @@ __global__ __launch_bounds__(512) void conv_patch256_kernel(GatherConvArgs a, in
   int tko[9];
 #pragma unroll
   for (int i = 0; i < 9; ++i) tko[i] = (a.tap[i] >> 16) * a.Ci * 2;   // byte offset of the tap's k block in a weight row
-  const int cpc = a.Ci >> 6;   // channel blocks
+  const int cpc = (a.Ci + 63) >> 6;   // channel blocks
+  // KTAIL (as in conv_patch_kernel): bit j (patch loads) / bit 16 + j (weight loads): this lane's unit exists in the
+  // last channel block; the others come from the zero word
+  unsigned tail_ok = 0;
+  uint32_t zero_lo = 0, zero_hi = 0;
+  if (KTAIL) {
+#pragma unroll
+    for (int j = 0; j < JX; ++j) {
+      const int p = 8 * (NWAVES * j + wave) + (lane >> 3);
+      const int u = (lane & 7) ^ ((p >> 1) & 7);
+      if ((cpc - 1) * 64 + u * 8 < a.Ci) tail_ok |= 1u << j;
+    }
+#pragma unroll
+    for (int j = 0; j < JW; ++j) {
+      const int row = 8 * (NWAVES * j + wave) + (lane >> 3);
+      const int u = (lane & 7) ^ ((row >> 1) & 7);
+      if ((cpc - 1) * 64 + u * 8 < a.Ci) tail_ok |= 1u << (16 + j);
+    }
+    const uint64_t z = (uint64_t)g_zero_word;
+    zero_lo = (uint32_t)z; zero_hi = (uint32_t)(z >> 32);
+    asm volatile("" : "+v"(zero_lo), "+v"(zero_hi));
+  }
+  static_assert(JX <= 16 && JW <= 16, "bits of tail_ok");
 
   auto issue_x_one = [&](int j, int c) {
     const char* base = reinterpret_cast<const char*>(a.in) + (size_t)c * 128;
-    dma16(base + (size_t)xoff[j], smem + (c & 1) * XBYTES + (8 * (NWAVES * j + wave)) * ROWB);
+    unsigned char* dst = smem + (c & 1) * XBYTES + (8 * (NWAVES * j + wave)) * ROWB;
+    if (KTAIL) {
+      const bool ok = c != cpc - 1 || ((tail_ok >> j) & 1u);
+      const uint64_t pa = (uint64_t)(base + (size_t)xoff[j]);
+      const uint32_t lo = ok ? (uint32_t)pa : zero_lo, hi = ok ? (uint32_t)(pa >> 32) : zero_hi;
+      dma16((const char*)(((uint64_t)hi << 32) | lo), dst);
+    } else {
+      dma16(base + (size_t)xoff[j], dst);
+    }
   };
-  auto issue_w_one = [&](int j, int slot, int kbyte) {
+  // cblock: the channel block the weights belong to
+  auto issue_w_one = [&](int j, int slot, int kbyte, int cblock) {
     const char* base = reinterpret_cast<const char*>(a.w) + (size_t)kbyte;
     const int row0 = 8 * (NWAVES * j + wave);   // rows past the stage: the load still happens, into the dump area
-    unsigned char* dst = row0 < BN ? smem + 2 * XBYTES + slot * WBYTES + row0 * ROWB : smem + DUMP + (wave & 3) * 1024;
-    dma16(base + (size_t)woff[j], dst);
+    unsigned char* dst = row0 < BN ? smem + 2 * XBYTES + slot * WBYTES + row0 * ROWB : smem + DUMP + (wave & 3) * DUMP_EACH;
+    if (KTAIL) {
+      const bool ok = cblock != cpc - 1 || ((tail_ok >> (16 + j)) & 1u);
+      const uint64_t pa = (uint64_t)(base + (size_t)woff[j]);
+      const uint32_t lo = ok ? (uint32_t)pa : zero_lo, hi = ok ? (uint32_t)(pa >> 32) : zero_hi;
+      dma16((const char*)(((uint64_t)hi << 32) | lo), dst);
+    } else {
+      dma16(base + (size_t)woff[j], dst);
+    }
   };
 #pragma unroll
   for (int j = 0; j < JX; ++j) issue_x_one(j, 0);
 #pragma unroll
   for (int p = 0; p < WS - 1; ++p)   // 9 taps >= WS - 1 steps always exist
 #pragma unroll
-    for (int j = 0; j < JW; ++j) issue_w_one(j, p, tko[p]);
+    for (int j = 0; j < JW; ++j) issue_w_one(j, p, tko[p], 0);
 
   f32x16 acc[FN][FM];
 #pragma unroll
@@ -733,7 +773,7 @@ __global__ __launch_bounds__(512) void conv_patch256_kernel(GatherConvArgs a, in
           }
           if constexpr (SS == 0 && MORE && (K == 2 || K == 3 || (K >= 5 && K % 2 == 1))) {
             constexpr int IDX = K <= 3 ? K - 2 : 2 + (K - 5) / 2;
-            if constexpr (IDX < NWL) issue_w_one(IDX, islot, kbyte);
+            if constexpr (IDX < NWL) issue_w_one(IDX, islot, kbyte, TT < 9 ? c : c + 1);
             else if constexpr (IDX - NWL < NX) issue_x_one(T * PER + IDX - NWL, c + 1);
           }
           __builtin_amdgcn_sched_barrier(0);
@@ -789,13 +829,14 @@ static hipError_t run_patch(const GatherConvArgs& a, hipStream_t s) {
   return a.Ci % 64 == 0 ? run_patch_k<BN, PR, false>(a, s) : run_patch_k<BN, PR, true>(a, s);
 }
 
-template <int BN, int PR, int WS>
+template <int BN, int PR, int WS, bool KTAIL>
 static hipError_t run_patch256(const GatherConvArgs& a, hipStream_t s) {
-  constexpr size_t lds = (size_t)2 * (PR * 128 + 256) + (size_t)WS * BN * 128 + 4096;
+  constexpr size_t body = (size_t)2 * (PR * 128 + 256) + (size_t)WS * BN * 128;
+  constexpr size_t lds = body + (body + 4096 <= 160 * 1024 ? 4096 : 1024);   // the kernel's LDS_BYTES
   static_assert(lds <= 160 * 1024, "LDS of one compute unit");
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_patch256_kernel<BN, PR, WS>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_patch256_kernel<BN, PR, WS, KTAIL>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     configured = true;
@@ -803,9 +844,9 @@ static hipError_t run_patch256(const GatherConvArgs& a, hipStream_t s) {
   const int Mtot = a.N * a.OH * a.OW;
   const int m_tiles = (Mtot + 255) / 256, n_tiles = (a.Co + BN - 1) / BN;
   static char name[64];
-  if (!name[0]) snprintf(name, sizeof(name), "conv_patch256_kernel<%d, %d, %d>", BN, PR, WS);
+  if (!name[0]) snprintf(name, sizeof(name), KTAIL ? "conv_patch256_kernel<%d, %d, %d, true>" : "conv_patch256_kernel<%d, %d, %d>", BN, PR, WS);
   note_kernel(name);
-  hipLaunchKernelGGL((conv_patch256_kernel<BN, PR, WS>), dim3(m_tiles * n_tiles), dim3(512), lds, s, a, m_tiles, n_tiles);
+  hipLaunchKernelGGL((conv_patch256_kernel<BN, PR, WS, KTAIL>), dim3(m_tiles * n_tiles), dim3(512), lds, s, a, m_tiles, n_tiles);
   return hipGetLastError();
 }
 
@@ -816,7 +857,10 @@ static hipError_t run_patch_rows(const GatherConvArgs& a, hipStream_t s) {
     static const bool off = getenv("FDG_PATCH_128") != nullptr;   // A/B switch for measurements
     const int Mtot = a.N * a.OH * a.OW, n_tiles = (a.Co + BN - 1) / BN;
     const int t128 = (Mtot + 127) / 128 * n_tiles, t256 = (Mtot + 255) / 256 * n_tiles;
-    if (!off && a.Ci % 64 == 0 && t128 > 256 && t256 >= 224 && 256 + 2 * a.Wi + 2 <= 320) return run_patch256<BN, 320, 3>(a, s);
+    if (!off && t128 > 256 && t256 >= 224) {
+      if (a.Ci % 64 != 0) return run_patch256<BN, 384, 3, true>(a, s);
+      return 256 + 2 * a.Wi + 2 <= 320 ? run_patch256<BN, 320, 3, false>(a, s) : run_patch256<BN, 384, 3, false>(a, s);
+    }
   }
   const int rows = 128 + 2 * a.Wi + 2;   // patch rows in use
   if (rows <= 160) return run_patch<BN, 160>(a, s);

@@ -34,8 +34,13 @@ FULL_CASES = [
     (128, 64, 64, 64, 64, 3, 1),
     (128, 32, 32, 3, 16, 3, 1),
     (128, 64, 64, 3, 64, 3, 1),
+    # WRN-28-10's 160-channel stage at 32x32 (the lower module of the K = 2 chain): 256-pixel tiles with a partly filled
+    # last channel block; the same with a ragged last tile; 128 channels on the 384-row patch
+    (128, 32, 32, 160, 160, 3, 1),
+    (61, 31, 32, 160, 160, 3, 1),
+    (128, 32, 32, 128, 128, 3, 1),
 ]
-IMAGES = [0, 63, 127]
+IMAGES = [0, 63, -1]   # first, one inside (modulo the batch), last
 
 
 def _t():
@@ -85,10 +90,11 @@ def test_conv_forward_and_data_gradient_on_sampled_images(case):
     stats = t.zeros(2 * co, dtype=t.float32, device="cuda")
     K.fdgk_conv_fwd(xd, wd, None, y32, y16, stats, n, h, w, ci, co, k, s)
     t.cuda.synchronize()
-    x_sel = x[IMAGES].transpose(0, 3, 1, 2).copy()
+    imgs = sorted({i % n for i in IMAGES})
+    x_sel = x[imgs].transpose(0, 3, 1, 2).copy()
     ref = K32.conv_fwd(x_sel, w_oihw, s, pad).astype(np.float64)       # [3, co, ho, wo]
-    got32 = y32[IMAGES].cpu().numpy().transpose(0, 3, 1, 2)
-    got16 = y16[IMAGES].to(t.float32).cpu().numpy().transpose(0, 3, 1, 2)
+    got32 = y32[imgs].cpu().numpy().transpose(0, 3, 1, 2)
+    got16 = y16[imgs].to(t.float32).cpu().numpy().transpose(0, 3, 1, 2)
     assert rel(got32, ref) <= F32_TOL
     assert rel(got16, ref) <= B16_TOL
     yb = y16.to(t.float64).reshape(-1, co)
@@ -104,10 +110,10 @@ def test_conv_forward_and_data_gradient_on_sampled_images(case):
     dx16 = t.zeros((n, h, w, cip), dtype=t.bfloat16, device="cuda")
     K.fdgk_conv_dgrad(dyd, wtd, None, None, dx32, dx16, n, h, w, ci, co, k, s)
     t.cuda.synchronize()
-    dy_sel = dy[IMAGES].transpose(0, 3, 1, 2).copy()
-    dref = K32.conv_bwd_data(dy_sel, w_oihw, (len(IMAGES), ci, h, w), s, pad).astype(np.float64)
-    assert rel(dx32[IMAGES][..., :ci].cpu().numpy().transpose(0, 3, 1, 2), dref) <= F32_TOL
-    assert rel(dx16[IMAGES][..., :ci].to(t.float32).cpu().numpy().transpose(0, 3, 1, 2), dref) <= B16_TOL
+    dy_sel = dy[imgs].transpose(0, 3, 1, 2).copy()
+    dref = K32.conv_bwd_data(dy_sel, w_oihw, (len(imgs), ci, h, w), s, pad).astype(np.float64)
+    assert rel(dx32[imgs][..., :ci].cpu().numpy().transpose(0, 3, 1, 2), dref) <= F32_TOL
+    assert rel(dx16[imgs][..., :ci].to(t.float32).cpu().numpy().transpose(0, 3, 1, 2), dref) <= B16_TOL
     assert bool((dx32[..., ci:] == 0).all())
     assert bool(t.isfinite(dx32).all())
 
