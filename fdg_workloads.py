@@ -26,9 +26,10 @@ BASIC_POSTACT = 1
 BASIC_PREACT = 2
 HEAD_POSTACT = 3
 HEAD_PREACT = 4
+BOTTLENECK_POSTACT = 5
 
 KIND_NAMES = {STEM: "stem", BASIC_POSTACT: "basic_postact", BASIC_PREACT: "basic_preact",
-              HEAD_POSTACT: "head_postact", HEAD_PREACT: "head_preact"}
+              HEAD_POSTACT: "head_postact", HEAD_PREACT: "head_preact", BOTTLENECK_POSTACT: "bottleneck_postact"}
 
 
 @dataclass(frozen=True)
@@ -44,7 +45,12 @@ class Layer:
 
     @property
     def projects(self) -> bool:
-        return self.kind in (BASIC_POSTACT, BASIC_PREACT) and (self.stride != 1 or self.c_in != self.c_out)
+        return self.kind in (BASIC_POSTACT, BASIC_PREACT, BOTTLENECK_POSTACT) and (self.stride != 1 or self.c_in != self.c_out)
+
+    @property
+    def c_mid(self) -> int:
+        """Channels inside a bottleneck block: a quarter of its output channels."""
+        return self.c_out // 4
 
 
 @dataclass
@@ -109,6 +115,17 @@ def param_shapes(spec: ModuleSpec) -> List[Tuple[str, Tuple[int, ...], str]]:
                     (p + "bn1.gamma", (L.c_out,), "gamma"), (p + "bn1.beta", (L.c_out,), "beta"),
                     (p + "conv2.w", (L.c_out, L.c_out, 3, 3), "conv"),
                     (p + "bn2.gamma", (L.c_out,), "gamma"), (p + "bn2.beta", (L.c_out,), "beta")]
+            if L.projects:
+                out += [(p + "proj.w", (L.c_out, L.c_in, 1, 1), "conv"),
+                        (p + "bnp.gamma", (L.c_out,), "gamma"), (p + "bnp.beta", (L.c_out,), "beta")]
+        elif L.kind == BOTTLENECK_POSTACT:
+            cm = L.c_mid
+            out += [(p + "conv1.w", (cm, L.c_in, 1, 1), "conv"),
+                    (p + "bn1.gamma", (cm,), "gamma"), (p + "bn1.beta", (cm,), "beta"),
+                    (p + "conv2.w", (cm, cm, 3, 3), "conv"),
+                    (p + "bn2.gamma", (cm,), "gamma"), (p + "bn2.beta", (cm,), "beta"),
+                    (p + "conv3.w", (L.c_out, cm, 1, 1), "conv"),
+                    (p + "bn3.gamma", (L.c_out,), "gamma"), (p + "bn3.beta", (L.c_out,), "beta")]
             if L.projects:
                 out += [(p + "proj.w", (L.c_out, L.c_in, 1, 1), "conv"),
                         (p + "bnp.gamma", (L.c_out,), "gamma"), (p + "bnp.beta", (L.c_out,), "beta")]
@@ -213,8 +230,8 @@ def _postact_stage(c_in: int, c_out: int, blocks: int, first_stride: int) -> Lis
 
 
 def config(idx: int, n: Optional[int] = None) -> ModuleSpec:
-    """Benchmark configuration idx in 1..7 (1..5: the CIFAR modules the metric is stated on; 6, 7: the two halves of
-    ResNet-18 at Tiny-ImageNet resolution, channel counts that are powers of two).  `n` overrides the batch size (for bounded CPU timing and
+    """Benchmark configuration idx in 1..8 (1..5: the CIFAR modules the metric is stated on; 6, 7: the two halves of
+    ResNet-18 at Tiny-ImageNet resolution, channel counts that are powers of two; 8: bottleneck blocks of ResNet-101).  `n` overrides the batch size (for bounded CPU timing and
     small parity cases); everything else keeps its real shape."""
     hyper = dict(momentum=0.9, weight_decay=5e-4, bn_eps=1e-5, bn_momentum=0.1, lr=0.1)
     if idx == 1:
@@ -258,7 +275,13 @@ def config(idx: int, n: Optional[int] = None) -> ModuleSpec:
         ls = [Layer(STEM, 3, 64, 1)] + _postact_stage(64, 64, 2, 1) + _postact_stage(64, 128, 2, 2)
         return ModuleSpec(n or 128, 3, 64, 64, ls, delay=1, is_bottom=True, beta=0.5,
                           name="cfg7 ResNet-18 Tiny-ImageNet K=2 module 0 (stem + blocks 1-4)", **hyper)
-    raise ValueError("config index must be 1..7")
+    if idx == 8:
+        # ResNet-101 at ImageNet resolution (Table VII's second network), K = 4, third module: eight bottleneck blocks of
+        # the 1024-channel stage (256 inside) at 14x14
+        ls = [Layer(BOTTLENECK_POSTACT, 1024, 1024, 1) for _ in range(8)]
+        return ModuleSpec(n or 128, 1024, 14, 14, ls, delay=1, is_bottom=False, beta=0.5,
+                          name="cfg8 ResNet-101 ImageNet K=4 module 2 (8 bottleneck blocks 1024/256 @14x14)", **hyper)
+    raise ValueError("config index must be 1..8")
 
 
 def conv_flops(spec: ModuleSpec) -> int:
@@ -275,7 +298,15 @@ def conv_flops(spec: ModuleSpec) -> int:
         ho, wo = (h - 1) // L.stride + 1, (w - 1) // L.stride + 1
         m = spec.n * ho * wo
         convs = []
-        if L.kind == STEM:
+        if L.kind == BOTTLENECK_POSTACT:
+            # the first 1x1 convolution runs at the input resolution; (ci, co, taps, reads the module input, pixels)
+            f1 = 2 * spec.n * h * w * L.c_in * L.c_mid
+            total += (2 if first and spec.is_bottom else 3) * f1
+            convs.append((L.c_mid, L.c_mid, 9, False))
+            convs.append((L.c_mid, L.c_out, 1, False))
+            if L.projects:
+                convs.append((L.c_in, L.c_out, 1, True))
+        elif L.kind == STEM:
             convs.append((L.c_in, L.c_out, 9, True))
         else:
             convs.append((L.c_in, L.c_out, 9, True))
@@ -285,7 +316,7 @@ def conv_flops(spec: ModuleSpec) -> int:
         for ci, co, taps, reads_module_input in convs:
             f = 2 * m * ci * co * taps
             passes = 3
-            if first and reads_module_input and spec.is_bottom and L.kind in (STEM, BASIC_POSTACT):
+            if first and reads_module_input and spec.is_bottom and L.kind in (STEM, BASIC_POSTACT, BOTTLENECK_POSTACT):
                 passes = 2
             total += passes * f
         first = False

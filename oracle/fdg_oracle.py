@@ -66,7 +66,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "fdg_oracle_kernels.c")
 
 # layer kinds, numerically equal to the C ABI's fdg_layer_kind (an interface constant)
-STEM, BASIC_POSTACT, BASIC_PREACT, HEAD_POSTACT, HEAD_PREACT = 0, 1, 2, 3, 4
+STEM, BASIC_POSTACT, BASIC_PREACT, HEAD_POSTACT, HEAD_PREACT, BOTTLENECK_POSTACT = 0, 1, 2, 3, 4, 5
 
 
 def lib_path(dtype) -> str:
@@ -226,7 +226,7 @@ class Kernels:
 
 
 def _projects(L) -> bool:
-    return L.kind in (BASIC_POSTACT, BASIC_PREACT) and (L.stride != 1 or L.c_in != L.c_out)
+    return L.kind in (BASIC_POSTACT, BASIC_PREACT, BOTTLENECK_POSTACT) and (L.stride != 1 or L.c_in != L.c_out)
 
 
 def oracle_param_layout(spec) -> List[Tuple[str, Tuple[int, ...]]]:
@@ -241,6 +241,13 @@ def oracle_param_layout(spec) -> List[Tuple[str, Tuple[int, ...]]]:
         elif L.kind == BASIC_POSTACT:
             out += [(f"{i}.conv1.w", (L.c_out, L.c_in, 3, 3))] + bn("bn1", L.c_out)
             out += [(f"{i}.conv2.w", (L.c_out, L.c_out, 3, 3))] + bn("bn2", L.c_out)
+            if _projects(L):
+                out += [(f"{i}.proj.w", (L.c_out, L.c_in, 1, 1))] + bn("bnp", L.c_out)
+        elif L.kind == BOTTLENECK_POSTACT:
+            cm = L.c_out // 4
+            out += [(f"{i}.conv1.w", (cm, L.c_in, 1, 1))] + bn("bn1", cm)
+            out += [(f"{i}.conv2.w", (cm, cm, 3, 3))] + bn("bn2", cm)
+            out += [(f"{i}.conv3.w", (L.c_out, cm, 1, 1))] + bn("bn3", L.c_out)
             if _projects(L):
                 out += [(f"{i}.proj.w", (L.c_out, L.c_in, 1, 1))] + bn("bnp", L.c_out)
         elif L.kind == BASIC_PREACT:
@@ -427,6 +434,21 @@ class OracleModule:
                     sc = z
                 t.update(a1=a1)
                 z = k.relu_fwd(b2 + sc)
+            elif L.kind == BOTTLENECK_POSTACT:
+                # 1x1 down to a quarter of the output channels, 3x3 (which carries the stride), 1x1 up, each followed
+                # by batch norm; ReLU after the first two and after the shortcut is added
+                c1 = q(k.conv_fwd(zb, th[f"{i}.conv1.w"], 1, 0))
+                a1 = q(k.relu_fwd(self._bn(f"{i}.bn1", c1, th, t)))
+                c2 = q(k.conv_fwd(a1, th[f"{i}.conv2.w"], L.stride, 1))
+                a2 = q(k.relu_fwd(self._bn(f"{i}.bn2", c2, th, t)))
+                c3 = q(k.conv_fwd(a2, th[f"{i}.conv3.w"], 1, 0))
+                b3 = self._bn(f"{i}.bn3", c3, th, t)
+                if _projects(L):
+                    sc = self._bn(f"{i}.bnp", q(k.conv_fwd(zb, th[f"{i}.proj.w"], L.stride, 0)), th, t)
+                else:
+                    sc = z
+                t.update(a1=a1, a2=a2)
+                z = k.relu_fwd(b3 + sc)
             elif L.kind == BASIC_PREACT:
                 o1 = q(k.relu_fwd(self._bn(f"{i}.bn1", zb, th, t)))
                 c1 = q(k.conv_fwd(o1, th[f"{i}.conv1.w"], L.stride, 1))
@@ -507,6 +529,28 @@ class OracleModule:
                     g[f"{i}.proj.w"][...] = k.conv_bwd_weight(x, dpr, 1, L.stride, 0)
                 if need_dx:
                     dx = k.conv_bwd_data(dc1, th[f"{i}.conv1.w"], x.shape, L.stride, 1)
+                    if _projects(L):
+                        dx = dx + k.conv_bwd_data(dpr, th[f"{i}.proj.w"], x.shape, L.stride, 0)
+                    else:
+                        dx = dx + ds
+                    dz = dx
+                else:
+                    dz = None
+            elif L.kind == BOTTLENECK_POSTACT:
+                ds = k.relu_bwd(t["y"], dz)                 # through the final ReLU; feeds both branches
+                dc3 = q(self._bn_back(f"{i}.bn3", ds, th, t, g))
+                g[f"{i}.conv3.w"][...] = k.conv_bwd_weight(t["a2"], dc3, 1, 1, 0)
+                da2 = q(k.conv_bwd_data(dc3, th[f"{i}.conv3.w"], t["a2"].shape, 1, 0))
+                dc2 = q(self._bn_back(f"{i}.bn2", k.relu_bwd(t["a2"], da2), th, t, g))
+                g[f"{i}.conv2.w"][...] = k.conv_bwd_weight(t["a1"], dc2, 3, L.stride, 1)
+                da1 = q(k.conv_bwd_data(dc2, th[f"{i}.conv2.w"], t["a1"].shape, L.stride, 1))
+                dc1 = q(self._bn_back(f"{i}.bn1", k.relu_bwd(t["a1"], da1), th, t, g))
+                g[f"{i}.conv1.w"][...] = k.conv_bwd_weight(x, dc1, 1, 1, 0)
+                if _projects(L):
+                    dpr = q(self._bn_back(f"{i}.bnp", ds, th, t, g))
+                    g[f"{i}.proj.w"][...] = k.conv_bwd_weight(x, dpr, 1, L.stride, 0)
+                if need_dx:
+                    dx = k.conv_bwd_data(dc1, th[f"{i}.conv1.w"], x.shape, 1, 0)
                     if _projects(L):
                         dx = dx + k.conv_bwd_data(dpr, th[f"{i}.proj.w"], x.shape, L.stride, 0)
                     else:

@@ -30,6 +30,10 @@ TINY = {
     "preact_widen": ModuleSpec(2, 4, 5, 5, [Layer(W.BASIC_PREACT, 4, 6, 1)]),
     "head_preact": ModuleSpec(3, 4, 4, 4, [Layer(W.BASIC_PREACT, 4, 4, 1), Layer(W.HEAD_PREACT, 4)], num_classes=5),
     "head_postact": ModuleSpec(3, 4, 4, 4, [Layer(W.BASIC_POSTACT, 4, 4, 1), Layer(W.HEAD_POSTACT, 4)], num_classes=5),
+    "bottleneck_identity": ModuleSpec(2, 8, 5, 5, [Layer(W.BOTTLENECK_POSTACT, 8, 8, 1)]),
+    "bottleneck_project": ModuleSpec(2, 4, 6, 6, [Layer(W.BOTTLENECK_POSTACT, 4, 8, 2)]),
+    "bottleneck_stack_head": ModuleSpec(3, 4, 6, 6, [Layer(W.BOTTLENECK_POSTACT, 4, 8, 1), Layer(W.BOTTLENECK_POSTACT, 8, 8, 2),
+                                                    Layer(W.HEAD_POSTACT, 8)], num_classes=5),
     "stack": ModuleSpec(2, 3, 8, 8, [Layer(W.STEM, 3, 4, 1), Layer(W.BASIC_POSTACT, 4, 4, 1),
                                     Layer(W.BASIC_POSTACT, 4, 8, 2), Layer(W.BASIC_POSTACT, 8, 8, 1)]),
 }

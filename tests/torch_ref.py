@@ -4,7 +4,7 @@ it shares nothing with oracle/ or with the HIP path."""
 import torch
 import torch.nn.functional as F
 
-STEM, BASIC_POSTACT, BASIC_PREACT, HEAD_POSTACT, HEAD_PREACT = 0, 1, 2, 3, 4
+STEM, BASIC_POSTACT, BASIC_PREACT, HEAD_POSTACT, HEAD_PREACT, BOTTLENECK_POSTACT = 0, 1, 2, 3, 4, 5
 
 
 def _bn(x, g, b, eps):
@@ -29,7 +29,7 @@ def forward(spec, params, x, labels=None):
     z = x
     eps = spec.bn_eps
     for L in spec.layers:
-        proj = L.kind in (BASIC_POSTACT, BASIC_PREACT) and (L.stride != 1 or L.c_in != L.c_out)
+        proj = L.kind in (BASIC_POSTACT, BASIC_PREACT, BOTTLENECK_POSTACT) and (L.stride != 1 or L.c_in != L.c_out)
         if L.kind == STEM:
             w, g, b = next(it), next(it), next(it)
             z = F.relu(_bn(F.conv2d(z, w, stride=L.stride, padding=1), g, b, eps))
@@ -37,6 +37,17 @@ def forward(spec, params, x, labels=None):
             w1, g1, b1, w2, g2, b2 = (next(it) for _ in range(6))
             a = F.relu(_bn(F.conv2d(z, w1, stride=L.stride, padding=1), g1, b1, eps))
             r = _bn(F.conv2d(a, w2, stride=1, padding=1), g2, b2, eps)
+            if proj:
+                wp, gp, bp = next(it), next(it), next(it)
+                sc = _bn(F.conv2d(z, wp, stride=L.stride), gp, bp, eps)
+            else:
+                sc = z
+            z = F.relu(r + sc)
+        elif L.kind == BOTTLENECK_POSTACT:
+            w1, g1, b1, w2, g2, b2, w3, g3, b3 = (next(it) for _ in range(9))
+            a = F.relu(_bn(F.conv2d(z, w1), g1, b1, eps))
+            a = F.relu(_bn(F.conv2d(a, w2, stride=L.stride, padding=1), g2, b2, eps))
+            r = _bn(F.conv2d(a, w3), g3, b3, eps)
             if proj:
                 wp, gp, bp = next(it), next(it), next(it)
                 sc = _bn(F.conv2d(z, wp, stride=L.stride), gp, bp, eps)
