@@ -63,6 +63,9 @@ typedef enum {
  *                       shortcut = x, or conv1x1(o, stride) when stride!=1 or c_in!=c_out
  *   HEAD_POSTACT      : global average pool -> FC(c_in->num_classes)+bias -> softmax cross-entropy
  *   HEAD_PREACT       : BN -> ReLU -> the same head
+ *   BOTTLENECK_POSTACT: conv1x1(c_in->c_out/4) -> BN -> ReLU -> conv3x3(c_out/4->c_out/4, stride) -> BN -> ReLU ->
+ *                       conv1x1(c_out/4->c_out) -> BN -> (+shortcut) -> ReLU, shortcut as in BASIC_POSTACT; the
+ *                       block of ResNet-101 (Section V-C, Table VII); c_out must be a multiple of 32
  * A head, if present, must be the last layer; the module is then a TOP module (Section III-B:
  * its gradient is not shrunk and it needs no gradient from above).                              */
 typedef enum {
@@ -70,7 +73,8 @@ typedef enum {
   FDG_BASIC_POSTACT = 1,
   FDG_BASIC_PREACT = 2,
   FDG_HEAD_POSTACT = 3,
-  FDG_HEAD_PREACT = 4
+  FDG_HEAD_PREACT = 4,
+  FDG_BOTTLENECK_POSTACT = 5
 } fdg_layer_kind;
 
 typedef struct {
@@ -164,6 +168,9 @@ void fdg_destroy(fdg_module* m);
  *                   proj w[c_out,c_in,1,1]
  *   HEAD_POSTACT  : fc W[num_classes,c_in], fc b[num_classes]
  *   HEAD_PREACT   : bn gamma[c_in], bn beta[c_in], fc W, fc b
+ *   BOTTLENECK_POSTACT : with m = c_out/4: conv1 w[m,c_in,1,1], bn1 gamma[m], bn1 beta[m], conv2 w[m,m,3,3], bn2 gamma,
+ *                   bn2 beta, conv3 w[c_out,m,1,1], bn3 gamma[c_out], bn3 beta[c_out], then if projecting:
+ *                   proj w[c_out,c_in,1,1], bnp gamma, bnp beta
  * `count` must equal fdg_param_count.                                                           */
 size_t fdg_param_count(const fdg_module* m);
 fdg_status fdg_set_params(fdg_module* m, const float* host_src, size_t count); /* momentum := 0 */

@@ -38,9 +38,9 @@ struct LayerPlan {
   int kind, c_in, c_out, stride;
   int Hi, Wi, Ho, Wo;
   bool projects;
-  int conv[3];                 // conv1, conv2, projection (or stem conv in [0])
-  int bn[3];                   // bn1, bn2, bnp (stem / head bn in [0])
-  size_t act[5];               // byte offsets of saved bf16 tensors in a slot (meaning depends on kind)
+  int conv[4];                 // conv1, conv2, projection (or stem conv in [0]); bottleneck: conv3 in [3]
+  int bn[4];                   // bn1, bn2, bnp (stem / head bn in [0]); bottleneck: bn3 in [3]
+  size_t act[6];               // byte offsets of saved bf16 tensors in a slot (meaning depends on kind)
   size_t out_b;                // byte offset of this layer's bf16 output in a slot (stream copy)
   size_t fc_w_off, fc_b_off;   // parameter arena (elements)
 };
@@ -128,8 +128,8 @@ bool build_plan(const fdg_module_desc* desc, int save_mode, Plan& p, fdg_status*
     const fdg_layer_desc& ld = p.layers[i];
     LayerPlan lp{};
     lp.kind = ld.kind; lp.c_in = ld.c_in; lp.c_out = ld.c_out; lp.stride = ld.stride;
-    lp.conv[0] = lp.conv[1] = lp.conv[2] = -1;
-    lp.bn[0] = lp.bn[1] = lp.bn[2] = -1;
+    lp.conv[0] = lp.conv[1] = lp.conv[2] = lp.conv[3] = -1;
+    lp.bn[0] = lp.bn[1] = lp.bn[2] = lp.bn[3] = -1;
     if (ld.c_in != c) return false;
     const bool head = ld.kind == FDG_HEAD_POSTACT || ld.kind == FDG_HEAD_PREACT;
     if (head) {
@@ -149,13 +149,15 @@ bool build_plan(const fdg_module_desc* desc, int save_mode, Plan& p, fdg_status*
       p.L.push_back(lp);
       break;
     }
-    if (ld.kind != FDG_STEM_CONV_BN_RELU && ld.kind != FDG_BASIC_POSTACT && ld.kind != FDG_BASIC_PREACT) return false;
+    if (ld.kind != FDG_STEM_CONV_BN_RELU && ld.kind != FDG_BASIC_POSTACT && ld.kind != FDG_BASIC_PREACT &&
+        ld.kind != FDG_BOTTLENECK_POSTACT) return false;
+    if (ld.kind == FDG_BOTTLENECK_POSTACT && ld.c_out % 32 != 0) { *why = FDG_ERR_UNSUPPORTED; return false; }
     if (ld.c_out <= 0 || (ld.stride != 1 && ld.stride != 2)) return false;
     if (ld.c_out % 8 != 0 || ld.c_out > 2048) { *why = FDG_ERR_UNSUPPORTED; return false; }
     if (ld.kind != FDG_STEM_CONV_BN_RELU && (c % 8 != 0 || c > 2048)) { *why = FDG_ERR_UNSUPPORTED; return false; }
     const int ho = (h - 1) / ld.stride + 1, wo = (w - 1) / ld.stride + 1;
     lp.Hi = h; lp.Wi = w; lp.Ho = ho; lp.Wo = wo;
-    lp.projects = ld.kind != FDG_STEM_CONV_BN_RELU && (ld.stride != 1 || ld.c_in != ld.c_out);
+    lp.projects = ld.kind != FDG_STEM_CONV_BN_RELU && (ld.stride != 1 || ld.c_in != ld.c_out);   // blocks only
     const size_t Ein = (size_t)N * h * w * round8(c), Eout = (size_t)N * ho * wo * ld.c_out;
     if (ld.kind == FDG_STEM_CONV_BN_RELU) {
       lp.conv[0] = add_conv(ld.c_out, c, 9, ld.stride, h, w);
@@ -178,6 +180,35 @@ bool build_plan(const fdg_module_desc* desc, int save_mode, Plan& p, fdg_status*
       lp.act[0] = save(Eout);  // c1
       lp.act[1] = save(Eout);  // a1
       lp.act[2] = save(Eout);  // c2
+      if (lp.projects) {
+        lp.conv[2] = add_conv(ld.c_out, c, 1, ld.stride, h, w);
+        lp.bn[2] = add_bn(ld.c_out, N * ho * wo);
+        pend.push_back({1, lp.conv[2], -1, 0, 0});
+        pend.push_back({0, -1, lp.bn[2], 0, (size_t)ld.c_out});
+        pend.push_back({0, -1, lp.bn[2], 1, (size_t)ld.c_out});
+        lp.act[3] = save(Eout);  // p
+      }
+    } else if (ld.kind == FDG_BOTTLENECK_POSTACT) {
+      const int cm = ld.c_out / 4;
+      const size_t Emid_in = (size_t)N * h * w * cm, Emid = (size_t)N * ho * wo * cm;
+      lp.conv[0] = add_conv(cm, c, 1, 1, h, w);
+      lp.bn[0] = add_bn(cm, N * h * w);
+      lp.conv[1] = add_conv(cm, cm, 9, ld.stride, h, w);
+      lp.bn[1] = add_bn(cm, N * ho * wo);
+      lp.conv[3] = add_conv(ld.c_out, cm, 1, 1, ho, wo);
+      lp.bn[3] = add_bn(ld.c_out, N * ho * wo);
+      const int order[3] = {0, 1, 3};
+      for (int q = 0; q < 3; ++q) {
+        const int bn = lp.bn[order[q]];
+        pend.push_back({1, lp.conv[order[q]], -1, 0, 0});
+        pend.push_back({0, -1, bn, 0, (size_t)p.bns[bn].C});
+        pend.push_back({0, -1, bn, 1, (size_t)p.bns[bn].C});
+      }
+      lp.act[0] = save(Emid_in);  // c1
+      lp.act[1] = save(Emid_in);  // a1
+      lp.act[2] = save(Emid);     // c2
+      lp.act[4] = save(Emid);     // a2
+      lp.act[5] = save(Eout);     // c3
       if (lp.projects) {
         lp.conv[2] = add_conv(ld.c_out, c, 1, ld.stride, h, w);
         lp.bn[2] = add_bn(ld.c_out, N * ho * wo);
@@ -664,6 +695,25 @@ fdg_status forward_pass(fdg_module* m, const SlotView& v, const float* x_dev, fl
       } else {
         FDG_TRY(bn_apply(m, v, b2, t_c2, m->S(cur), nullptr, nullptr, m->S(nxt), v.act(L.out_b), replayed, s));
       }
+    } else if (L.kind == FDG_BOTTLENECK_POSTACT) {
+      const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]], &c3 = p.convs[L.conv[3]];
+      const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]], &b3 = p.bns[L.bn[3]];
+      bf16_t *t_c1 = v.act(L.act[0]), *t_a1 = v.act(L.act[1]), *t_c2 = v.act(L.act[2]), *t_a2 = v.act(L.act[4]),
+             *t_c3 = v.act(L.act[5]);
+      FDG_TRY(mconv_forward(m, c1, cur_b, v.W(c1), nullptr, nullptr, t_c1, v.sums(b1), s));
+      FDG_TRY(bn_apply(m, v, b1, t_c1, nullptr, nullptr, nullptr, nullptr, t_a1, replayed, s));
+      FDG_TRY(mconv_forward(m, c2, t_a1, v.W(c2), nullptr, nullptr, t_c2, v.sums(b2), s));
+      FDG_TRY(bn_apply(m, v, b2, t_c2, nullptr, nullptr, nullptr, nullptr, t_a2, replayed, s));
+      FDG_TRY(mconv_forward(m, c3, t_a2, v.W(c3), nullptr, nullptr, t_c3, v.sums(b3), s));
+      if (L.projects) {
+        const ConvInfo& cp = p.convs[L.conv[2]];
+        const BnInfo& bp = p.bns[L.bn[2]];
+        bf16_t* t_p = v.act(L.act[3]);
+        FDG_TRY(mconv_forward(m, cp, cur_b, v.W(cp), nullptr, nullptr, t_p, v.sums(bp), s));
+        FDG_TRY(bn_apply(m, v, b3, t_c3, nullptr, &bp, t_p, m->S(nxt), v.act(L.out_b), replayed, s));
+      } else {
+        FDG_TRY(bn_apply(m, v, b3, t_c3, m->S(cur), nullptr, nullptr, m->S(nxt), v.act(L.out_b), replayed, s));
+      }
     } else if (L.kind == FDG_BASIC_PREACT) {
       const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]];
       const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]];
@@ -889,6 +939,30 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
         } else {
           FDG_TRY(mconv_dgrad(m, c1, m->T(0), v.Wt(c1), m->G(cur), t_y, m->G(nxt), m->GB(nxt), s));
         }
+      }
+    } else if (L.kind == FDG_BOTTLENECK_POSTACT) {
+      const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]], &c3 = p.convs[L.conv[3]];
+      const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]], &b3 = p.bns[L.bn[3]];
+      const bf16_t *t_c1 = v.act(L.act[0]), *t_a1 = v.act(L.act[1]), *t_c2 = v.act(L.act[2]), *t_a2 = v.act(L.act[4]),
+                   *t_c3 = v.act(L.act[5]), *t_y = v.act(L.out_b);
+      // final ReLU mask (y > 0) then BN3; then twice: weight gradient, data gradient through ReLU and batch norm
+      FDG_TRY(bn_backward(m, v, b3, m->G(cur), true, t_y, t_c3, nullptr, nullptr, m->T(0), s));
+      FDG_TRY(mconv_wgrad(m, c3, t_a2, m->T(0), s));
+      FDG_TRY(dgrad_relu_bn_backward(m, v, c3, m->T(0), v.Wt(c3), nullptr, b2, t_a2, t_c2, m->T(1), nullptr, nullptr, m->T(0), s));
+      FDG_TRY(mconv_wgrad(m, c2, t_a1, m->T(0), s));
+      FDG_TRY(dgrad_relu_bn_backward(m, v, c2, m->T(0), v.Wt(c2), nullptr, b1, t_a1, t_c1, m->T(1), nullptr, nullptr, m->T(0), s));
+      FDG_TRY(mconv_wgrad(m, c1, in_b, m->T(0), s));
+      if (L.projects) {
+        const ConvInfo& cp = p.convs[L.conv[2]];
+        const BnInfo& bp = p.bns[L.bn[2]];
+        FDG_TRY(bn_backward(m, v, bp, m->G(cur), true, t_y, v.act(L.act[3]), nullptr, nullptr, m->T(1), s));
+        FDG_TRY(mconv_wgrad(m, cp, in_b, m->T(1), s));
+        if (need_dx) {
+          FDG_TRY(mconv_dgrad(m, cp, m->T(1), v.Wt(cp), nullptr, nullptr, m->TPB(), nullptr, s));
+          FDG_TRY(mconv_dgrad(m, c1, m->T(0), v.Wt(c1), m->TPB(), nullptr, m->G(nxt), m->GB(nxt), s));
+        }
+      } else if (need_dx) {
+        FDG_TRY(mconv_dgrad(m, c1, m->T(0), v.Wt(c1), m->G(cur), t_y, m->G(nxt), m->GB(nxt), s));
       }
     } else {  // pre-activation block: y = conv2(o2) + shortcut
       const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]];

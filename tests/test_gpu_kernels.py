@@ -95,6 +95,12 @@ CONV_CASES = [  # n, h, w, ci, co, ksize, stride
     (2, 1, 7, 32, 32, 3, 1),
     (2, 7, 1, 16, 16, 3, 1),
     (3, 2, 2, 64, 64, 3, 1),
+    # the 1x1 convolutions of bottleneck blocks: down to a quarter of the channels and back up
+    (16, 16, 16, 128, 32, 1, 1),
+    (16, 16, 16, 32, 128, 1, 1),
+    (4, 14, 14, 1024, 256, 1, 1),
+    (4, 14, 14, 256, 1024, 1, 1),
+    (4, 14, 14, 256, 256, 3, 1),
 ]
 
 

@@ -41,6 +41,17 @@ ENVELOPE = {
     "postact_wide": ModuleSpec(16, 96, 16, 16, [Layer(W.BASIC_POSTACT, 96, 160, 1)], delay=0, beta=1.0, **H),
     "preact_wide": ModuleSpec(16, 160, 16, 16, [Layer(W.BASIC_PREACT, 160, 320, 2), Layer(W.BASIC_PREACT, 320, 320, 1)],
                               delay=0, beta=1.0, **H),
+    # Bottleneck blocks: three ReLU gates in a row and a 1x1 convolution over only c_out/4 channels behind the second.
+    # Differences the size of a changed summation order in a convolution (3e-7 of its output) move the oracle's OWN
+    # gradients of the first case by 4e-3 .. 1.3e-2 in L2 and up to 0.27 of max |grad_in|, thirty times what the same
+    # noise does to a basic block of the same size (tests/test_oracle_module.py shows it on the CPU): a few values
+    # rounded to the neighbouring bf16 reach thousands of pre-activations of the last ReLU through the 1x1 convolution.
+    "bottleneck_identity": ModuleSpec(16, 128, 16, 16, [Layer(W.BOTTLENECK_POSTACT, 128, 128, 1)], delay=0, beta=0.5, **H),
+    "bottleneck_project_delay1": ModuleSpec(16, 64, 32, 32, [Layer(W.BOTTLENECK_POSTACT, 64, 128, 2)], delay=1, beta=0.5, **H),
+    "bottleneck_ragged": ModuleSpec(3, 32, 7, 9, [Layer(W.BOTTLENECK_POSTACT, 32, 64, 2), Layer(W.BOTTLENECK_POSTACT, 64, 64, 1)],
+                                    delay=0, beta=0.5, **H),
+    "bottleneck_wide_head": ModuleSpec(16, 256, 14, 14, [Layer(W.BOTTLENECK_POSTACT, 256, 512, 1), Layer(W.BOTTLENECK_POSTACT, 512, 512, 2),
+                                                         Layer(W.HEAD_POSTACT, 512)], delay=0, num_classes=10, **H),
     "bottom_stack_delay2": ModuleSpec(4, 3, 16, 16, [Layer(W.STEM, 3, 16, 1), Layer(W.BASIC_POSTACT, 16, 16, 1),
                                                      Layer(W.BASIC_POSTACT, 16, 32, 2), Layer(W.BASIC_POSTACT, 32, 32, 1)],
                                       delay=2, is_bottom=True, beta=0.2, **H),
@@ -81,7 +92,7 @@ def test_config1_basic_block_full_size():
     _check(W.config(1), steps=3, strict=True, perturb_bn=False)
 
 
-@pytest.mark.parametrize("idx,n,steps", [(2, 16, 2), (3, 16, 2), (4, 8, 1), (5, 8, 1), (6, 8, 1), (7, 4, 2)])
+@pytest.mark.parametrize("idx,n,steps", [(2, 16, 2), (3, 16, 2), (4, 8, 1), (5, 8, 1), (6, 8, 1), (7, 4, 2), (8, 8, 2)])
 def test_configs_reduced_batch(idx, n, steps):
     """The benchmark modules at their real layer shapes, with a batch the oracle finishes in seconds."""
     spec = W.config(idx, n=n)

@@ -40,7 +40,7 @@ def test_replay_shallow_modules_meet_the_strict_bar(name):
     _check(spec, steps=2, strict=True, seed=1)
 
 
-@pytest.mark.parametrize("name", ["head_preact", "postact_project_ragged", "preact_wide", "bottom_stack_delay2"])
+@pytest.mark.parametrize("name", ["head_preact", "postact_project_ragged", "preact_wide", "bottom_stack_delay2", "bottleneck_project_delay1"])
 def test_replay_ragged_wide_and_stacked_modules(name):
     spec = copy.deepcopy(ENVELOPE[name])
     spec.name = name

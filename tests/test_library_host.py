@@ -37,7 +37,7 @@ def test_status_strings():
     assert b"queue" in lib.fdg_status_string(4)
 
 
-@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6, 7, 8])
 def test_workspace_bytes_of_benchmark_configs(idx):
     spec = W.config(idx)
     b = binding.fdg_module_workspace_bytes(spec)
@@ -47,7 +47,7 @@ def test_workspace_bytes_of_benchmark_configs(idx):
     assert binding.fdg_module_workspace_bytes(deeper) > b      # one more ring slot
 
 
-@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6, 7, 8])
 def test_workspace_bytes_when_a_saved_forward_is_its_input(idx):
     """FDG_SAVE_INPUT_AND_REPLAY: one set of intermediates for the module instead of one per ring slot; a slot is the
     weight snapshot plus the fp32 input."""
