@@ -499,7 +499,19 @@ static hipError_t conv_dgrad_impl(const ConvShape& c, const bf16_t* dy, const bf
   return hipSuccess;
 }
 
-size_t conv_wgrad_scratch_bytes(const ConvShape& c) {
+// A 1x1 convolution with unit stride does not see the image: its pixels are one long list, and the weight-gradient
+// kernels that take whole rows of 1, 2, .. 32 or 64 pixels per 64-pixel step (conv_wgrad128_applies and the others)
+// get it as images of two rows of 32, whatever the real width (14 x 14 in ResNet-101's third stage).
+static ConvShape wgrad_view(const ConvShape& c) {
+  const long long pixels = (long long)c.N * c.Hi * c.Wi;
+  if (c.T != 1 || c.stride != 1 || pixels % 64 != 0 || pixels / 64 > 0x7fffffff || (c.Wi >= 1 && 64 % c.Wi == 0)) return c;
+  ConvShape v = c;
+  v.N = (int)(pixels / 64); v.Hi = 2; v.Wi = 32;
+  return v;
+}
+
+size_t conv_wgrad_scratch_bytes(const ConvShape& c_in) {
+  const ConvShape c = wgrad_view(c_in);
   WgradArgs a{};
   a.Co = c.Co; a.Ci = c.Ci; a.Cx = c.Cip; a.OW = c.Wo(); a.ntaps = c.T;
   a.N = c.N; a.OH = c.Ho(); a.Hi = c.Hi; a.Wi = c.Wi; a.stride = c.stride;
@@ -518,8 +530,9 @@ size_t conv_wgrad_scratch_bytes(const ConvShape& c) {
   return splits * c.Co * c.T * c.Ci * 4;
 }
 
-hipError_t conv_wgrad(const ConvShape& c, const bf16_t* x, const bf16_t* dy, float* dw, float* scratch,
+hipError_t conv_wgrad(const ConvShape& c_in, const bf16_t* x, const bf16_t* dy, float* dw, float* scratch,
                       size_t scratch_bytes, bool overwrite, hipStream_t s) {
+  const ConvShape c = wgrad_view(c_in);
   WgradArgs a{};
   a.dy = dy; a.x = x; a.dw = dw; a.scratch = scratch; a.scratch_bytes = scratch_bytes;
   a.overwrite = overwrite ? 1 : 0;

@@ -39,6 +39,10 @@ FULL_CASES = [
     (128, 32, 32, 160, 160, 3, 1),
     (61, 31, 32, 160, 160, 3, 1),
     (128, 32, 32, 128, 128, 3, 1),
+    # the layers of a ResNet-101 bottleneck block of the 1024-channel stage at 14x14
+    (128, 14, 14, 1024, 256, 1, 1),
+    (128, 14, 14, 256, 256, 3, 1),
+    (128, 14, 14, 256, 1024, 1, 1),
 ]
 IMAGES = [0, 63, -1]   # first, one inside (modulo the batch), last
 

@@ -101,6 +101,8 @@ CONV_CASES = [  # n, h, w, ci, co, ksize, stride
     (4, 14, 14, 1024, 256, 1, 1),
     (4, 14, 14, 256, 1024, 1, 1),
     (4, 14, 14, 256, 256, 3, 1),
+    (16, 14, 14, 256, 128, 1, 1),   # pixels a multiple of 64, width not a divisor of 64: the weight gradient sees rows of 32
+    (16, 14, 14, 128, 256, 1, 1),
 ]
 
 
