@@ -47,8 +47,15 @@ __device__ __forceinline__ void wait_vmcnt() {
 // 128 x 160 tile) and the two k-halves are added once, through LDS, after the main loop.
 // KTAIL: the input channels are not a multiple of 64 (WRN's 160): the last 64-channel chunk of every tap is
 // partly beyond the tensor, and those 16-byte units are loaded from the zero word, for pixels and weights alike.
+constexpr size_t gather_dma_lds_bytes(int BN, int STAGES) {
+  size_t need = (size_t)STAGES * (128 + BN) * 128;
+  if (need < (size_t)4 * (BN / 32) * 16 * 256) need = (size_t)4 * (BN / 32) * 16 * 256;
+  if (need < (size_t)4 * out_stage_bytes(BN) + stats_stage_bytes(BN)) need = (size_t)4 * out_stage_bytes(BN) + stats_stage_bytes(BN);
+  return need;
+}
+
 template <int BN, int STAGES, bool KTAIL>
-__global__ __launch_bounds__(256) void conv_gather_dma_kernel(GatherConvArgs a, int m_tiles, int n_tiles) {
+__device__ __forceinline__ void gather_dma_body(const GatherConvArgs& a, int m_tiles, int n_tiles) {
   constexpr int BM = 128;
   static_assert(BN % 32 == 0, "whole 32x32 blocks");
   constexpr int ROWB = 128;                 // bytes per LDS row = 64 bf16 of one tap
@@ -57,8 +64,7 @@ __global__ __launch_bounds__(256) void conv_gather_dma_kernel(GatherConvArgs a, 
   constexpr int NJ = JX + JW;
   constexpr int FM = 2, FN = BN / 32;
   static_assert((STAGES - 2) * NJ < 64, "vmcnt range");
-  static_assert((size_t)STAGES * R * ROWB >= (size_t)4 * FN * 16 * 256 && (size_t)STAGES * R * ROWB >= (size_t)4 * out_stage_bytes(BN) + stats_stage_bytes(BN), "room for the output stage");
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // STAGES * R * ROWB
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // gather_dma_lds_bytes(BN, STAGES): stages, or the output stage if larger
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: it selects DMA destinations
@@ -178,6 +184,17 @@ __global__ __launch_bounds__(256) void conv_gather_dma_kernel(GatherConvArgs a, 
   }
   wait_vmcnt<0>();
   combine_and_store32<FN, BN>(b, acc, m0, c0, wave_m, wk, lane, smem);
+}
+
+template <int BN, int STAGES, bool KTAIL>
+__global__ __launch_bounds__(256) void conv_gather_dma_kernel(GatherConvArgs a, int m_tiles, int n_tiles) {
+  gather_dma_body<BN, STAGES, KTAIL>(a, m_tiles, n_tiles);
+}
+// The same within 256 registers, so that two workgroups (two waves per SIMD) fit a compute unit: for the two-stage form.
+template <int BN, int STAGES, bool KTAIL>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void conv_gather_dma_pair_kernel(
+    GatherConvArgs a, int m_tiles, int n_tiles) {
+  gather_dma_body<BN, STAGES, KTAIL>(a, m_tiles, n_tiles);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -876,7 +893,8 @@ bool conv_gather_wide_applies(const GatherConvArgs& a) {
 
 template <int BN, int STAGES, bool KTAIL>
 static hipError_t run_wide_k(const GatherConvArgs& a, hipStream_t s) {
-  constexpr size_t lds = (size_t)STAGES * (128 + BN) * 128;
+  constexpr size_t lds = gather_dma_lds_bytes(BN, STAGES);
+  static_assert(lds <= 160 * 1024, "LDS of one compute unit");
   static bool configured = false;   // one attribute call per instantiation (idempotent, so a race is harmless)
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_gather_dma_kernel<BN, STAGES, KTAIL>),
@@ -906,6 +924,23 @@ static hipError_t run_wide_k(const GatherConvArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+static hipError_t run_wide_pair(const GatherConvArgs& a, hipStream_t s) {
+  constexpr int BN = 128, STAGES = 2;
+  constexpr size_t lds = gather_dma_lds_bytes(BN, STAGES);
+  static_assert(2 * lds <= 160 * 1024, "two workgroups in the LDS of one compute unit");
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_gather_dma_pair_kernel<BN, STAGES, false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  note_kernel("conv_gather_dma_pair_kernel<128, 2>");
+  const int m_tiles = (a.N * a.OH * a.OW + 127) / 128, n_tiles = (a.Co + BN - 1) / BN;
+  hipLaunchKernelGGL((conv_gather_dma_pair_kernel<BN, STAGES, false>), dim3(m_tiles * n_tiles), dim3(256), lds, s, a, m_tiles, n_tiles);
+  return hipGetLastError();
+}
+
 template <int BN, int STAGES>
 static hipError_t run_wide(const GatherConvArgs& a, hipStream_t s) {
   return a.Ci % 64 == 0 ? run_wide_k<BN, STAGES, false>(a, s) : run_wide_k<BN, STAGES, true>(a, s);
@@ -920,6 +955,13 @@ hipError_t launch_conv_gather_wide(const GatherConvArgs& a, hipStream_t s) {
   static const bool no_patch = getenv("FDG_NO_PATCH") != nullptr;
   if (conv_patch_applies(a) && !no_patch) return a.Co % 160 == 0 ? run_patch_rows<160>(a, s) : run_patch_rows<128>(a, s);
   if (a.Co % 160 == 0) return run_wide<160, 4>(a, s);
+  // A short contraction over many tiles (a 1x1 convolution from few channels: 4 steps per tile): two stages instead of
+  // four are 64 KB of LDS, so two workgroups share a compute unit and one's output stage runs beside the other's loads
+  // and main loop.
+  const int steps = a.ntaps * ((a.Ci + 63) / 64);
+  const long tiles = (long)((a.N * a.OH * a.OW + 127) / 128) * ((a.Co + 127) / 128);
+  static const bool no_short = getenv("FDG_NO_SHORT_K") != nullptr;   // A/B switch for measurements
+  if (!no_short && a.nclass <= 1 && steps <= 4 && tiles >= 1024 && a.Ci % 64 == 0) return run_wide_pair(a, s);
   return run_wide<128, 4>(a, s);
 }
 

@@ -43,6 +43,7 @@ FULL_CASES = [
     (128, 14, 14, 1024, 256, 1, 1),
     (128, 14, 14, 256, 256, 3, 1),
     (128, 14, 14, 256, 1024, 1, 1),
+    (127, 14, 14, 256, 1024, 1, 1),   # a ragged last pixel tile in the two-workgroups-per-unit form of the short contraction
 ]
 IMAGES = [0, 63, -1]   # first, one inside (modulo the batch), last
 
