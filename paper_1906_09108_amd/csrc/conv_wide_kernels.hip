@@ -955,13 +955,15 @@ hipError_t launch_conv_gather_wide(const GatherConvArgs& a, hipStream_t s) {
   static const bool no_patch = getenv("FDG_NO_PATCH") != nullptr;
   if (conv_patch_applies(a) && !no_patch) return a.Co % 160 == 0 ? run_patch_rows<160>(a, s) : run_patch_rows<128>(a, s);
   if (a.Co % 160 == 0) return run_wide<160, 4>(a, s);
-  // A short contraction over many tiles (a 1x1 convolution from few channels: 4 steps per tile): two stages instead of
-  // four are 64 KB of LDS, so two workgroups share a compute unit and one's output stage runs beside the other's loads
-  // and main loop.
+  // A short contraction (a 1x1 convolution: at most 16 steps per tile) over more tiles than compute units: two stages
+  // instead of four are 75 KB of LDS, so two workgroups share a compute unit, one's output stage runs beside the
+  // other's loads and main loop, and 257 .. 512 tiles take one round instead of two.
   const int steps = a.ntaps * ((a.Ci + 63) / 64);
   const long tiles = (long)((a.N * a.OH * a.OW + 127) / 128) * ((a.Co + 127) / 128);
   static const bool no_short = getenv("FDG_NO_SHORT_K") != nullptr;   // A/B switch for measurements
-  if (!no_short && a.nclass <= 1 && steps <= 4 && tiles >= 1024 && a.Ci % 64 == 0) return run_wide_pair(a, s);
+  static const int pair_steps = getenv("FDG_PAIR_STEPS") ? atoi(getenv("FDG_PAIR_STEPS")) : 16;     // for measurements
+  static const int pair_tiles = getenv("FDG_PAIR_TILES") ? atoi(getenv("FDG_PAIR_TILES")) : 300;
+  if (!no_short && a.nclass <= 1 && steps <= pair_steps && tiles >= pair_tiles && a.Ci % 64 == 0) return run_wide_pair(a, s);
   return run_wide<128, 4>(a, s);
 }
 
