@@ -1189,6 +1189,7 @@ struct Wgrad128Launch {
   size_t split_stride;
   int period;            // row validity repeats every `period` chunks
   int d_oh;              // output rows per chunk (64 / OW), reduced mod OH
+  int step_w;            // flat form (any width, unit stride): a chunk moves a pixel by 64 = d_oh rows and step_w columns
   long long a_step, b_step;   // bytes from one chunk to the next in dy and in x
 };
 
@@ -1465,7 +1466,11 @@ __global__ __launch_bounds__(256) void conv_wgrad128_kernel(WgradArgs a, Wgrad12
 // one's MFMAs run.  Fragments are double buffered (a step's reads are issued during the step before it, two per
 // MFMA slot), next-chunk / still-loading are compile-time tags, load addresses are 32-bit offsets from two
 // uniform pointers that advance with the chunk.
-template <int STAGES>
+// FLAT: unit stride and any image width.  The input pixel of output pixel P under tap (dh, dw) is P + dh W + dw
+// wherever it exists, so chunks need not start a row: the x pointer advances 64 pixels per chunk, and only the
+// validity of a lane's pixel (does the tap stay inside the image?) depends on where the chunk starts; it repeats
+// every OH OW / gcd(64, OH OW) chunks (49 for 7, 14, 28 and 56 pixels square), one bit of a 64-bit mask each.
+template <int STAGES, bool FLAT>
 __global__ __launch_bounds__(512) void conv_wgrad128w8_kernel(WgradArgs a, Wgrad128Launch L) {
   constexpr int BC = 128, BKP = 64, ROWB = BC * 2, PART = BKP * ROWB, STAGE = 2 * PART, NT = 512, NW = NT / 64;
   constexpr int JP = BKP * (BC / 8) / NT, NJ = 2 * JP;   // loads per thread, chunk and operand: 2
@@ -1495,28 +1500,43 @@ __global__ __launch_bounds__(512) void conv_wgrad128w8_kernel(WgradArgs a, Wgrad
   //      pointer starts one input row and one pixel before the chunk's first pixel, so that the offsets of taps
   //      that reach backwards stay non-negative (rows outside the image are never loaded) ----
   const int m0 = chunk_lo * BKP;
-  const int oh0 = (m0 / a.OW) % a.OH, n0 = m0 / (a.OW * a.OH);    // BKP % OW == 0: m0 starts an output row
+  const int oh0 = (m0 / a.OW) % a.OH, n0 = m0 / (a.OW * a.OH);    // not FLAT: BKP % OW == 0, m0 starts an output row
   const long long xrow0 = (long long)n0 * a.Hi + oh0 * a.stride;
   const int margin = (a.Wi + 1) * a.Cx * 2;
   const char* a_next = reinterpret_cast<const char*>(a.dy) + (size_t)m0 * a.Co * 2;
-  const char* b_next = reinterpret_cast<const char*>(a.x) + xrow0 * a.Wi * a.Cx * 2 - margin;
-  unsigned aoff32[JP], boff32[JP], bmask[JP];
+  const char* b_next = reinterpret_cast<const char*>(a.x) + (FLAT ? (long long)m0 : xrow0 * a.Wi) * a.Cx * 2 - margin;
+  typedef typename std::conditional<FLAT, unsigned long long, unsigned>::type mask_t;
+  unsigned aoff32[JP], boff32[JP];
+  mask_t bmask[JP];
 #pragma unroll
   for (int j = 0; j < JP; ++j) {
     const int P = 64 * (NW * j + wave) + lane;
     const int r = P >> 4, up = P & 15;
     const int u = 2 * ((up >> 1) ^ (2 * (r & 3))) + (up & 1);           // 256-byte rows: slot ^ 2 * (pixel & 3)
     aoff32[j] = (unsigned)((r * a.Co + co0 + u * 8) * 2);
-    const int ow = r % a.OW, orow = r / a.OW;
-    const int iw = ow * a.stride + dw;
-    const bool colok = (unsigned)iw < (unsigned)a.Wi;
-    boff32[j] = (unsigned)(margin + (((orow * a.stride + dh) * a.Wi + iw) * a.Cx + ci0 + u * 8) * 2);
-    unsigned mask = 0;
-    int ohq = (oh0 + orow) % a.OH;
-    for (int q = 0; q < L.period; ++q) {
-      if (colok && (unsigned)(ohq * a.stride + dh) < (unsigned)a.Hi) mask |= 1u << q;
-      ohq += L.d_oh;
-      if (ohq >= a.OH) ohq -= a.OH;
+    mask_t mask = 0;
+    if constexpr (FLAT) {
+      boff32[j] = (unsigned)(margin + ((r + dh * a.Wi + dw) * a.Cx + ci0 + u * 8) * 2);
+      int ow = (m0 + r) % a.OW, oh = ((m0 + r) / a.OW) % a.OH;
+      for (int q = 0; q < L.period; ++q) {
+        if ((unsigned)(ow + dw) < (unsigned)a.Wi && (unsigned)(oh + dh) < (unsigned)a.Hi) mask |= (mask_t)1 << q;
+        ow += L.step_w;
+        const int carry = ow >= a.OW ? 1 : 0;
+        ow -= carry * a.OW;
+        oh += L.d_oh + carry;          // d_oh < OH: below 2 OH
+        if (oh >= a.OH) oh -= a.OH;
+      }
+    } else {
+      const int ow = r % a.OW, orow = r / a.OW;
+      const int iw = ow * a.stride + dw;
+      const bool colok = (unsigned)iw < (unsigned)a.Wi;
+      boff32[j] = (unsigned)(margin + (((orow * a.stride + dh) * a.Wi + iw) * a.Cx + ci0 + u * 8) * 2);
+      int ohq = (oh0 + orow) % a.OH;
+      for (int q = 0; q < L.period; ++q) {
+        if (colok && (unsigned)(ohq * a.stride + dh) < (unsigned)a.Hi) mask |= (mask_t)1 << q;
+        ohq += L.d_oh;
+        if (ohq >= a.OH) ohq -= a.OH;
+      }
     }
     bmask[j] = mask;
   }
@@ -1525,8 +1545,8 @@ __global__ __launch_bounds__(512) void conv_wgrad128w8_kernel(WgradArgs a, Wgrad
   asm volatile("" : "+s"(zero_lo), "+s"(zero_hi));   // kept in two registers (rebuilt from the program counter otherwise)
 
   const unsigned lds0 = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)smem);
-  unsigned phase_bit = 1u;                 // 1 << ((chunk being issued) mod period)
-  const unsigned last_phase_bit = 1u << (L.period - 1);
+  mask_t phase_bit = 1;                    // 1 << ((chunk being issued) mod period)
+  const mask_t last_phase_bit = (mask_t)1 << (L.period - 1);
   unsigned issue_stage = 0;                // LDS byte offset of the stage being filled
   auto issue_one = [&](int d) {
     unsigned char* stage = smem + issue_stage;
@@ -1541,7 +1561,7 @@ __global__ __launch_bounds__(512) void conv_wgrad128w8_kernel(WgradArgs a, Wgrad
     }
   };
   auto issue_done = [&]() {
-    phase_bit = phase_bit == last_phase_bit ? 1u : phase_bit << 1;
+    phase_bit = phase_bit == last_phase_bit ? (mask_t)1 : phase_bit << 1;
     issue_stage = issue_stage == (STAGES - 1) * STAGE ? 0u : issue_stage + STAGE;
     a_next += L.a_step;
     b_next += L.b_step;
@@ -1708,9 +1728,20 @@ __global__ __launch_bounds__(512) void conv_wgrad128w8_kernel(WgradArgs a, Wgrad
   }
 }
 
+// Chunks per repetition of the flat form's validity pattern (0: the flat form does not apply): unit stride, any width.
+static int wgrad128_flat_period(const WgradArgs& a) {
+  if (a.stride != 1 || a.Hi != a.OH || a.Wi != a.OW || a.OW < 1 || a.OH < 1) return 0;
+  const long long img = (long long)a.OH * a.OW;
+  long long g = img, h = 64;
+  while (h) { const long long r = g % h; g = h; h = r; }
+  const long long period = img / g;
+  return period <= 64 ? (int)period : 0;
+}
+
 bool conv_wgrad128_applies(const WgradArgs& a) {
   if (a.Co % 128 != 0 || a.Ci % 128 != 0 || a.Cx != a.Ci || a.ntaps < 1) return false;
-  if (a.OW < 1 || 64 % a.OW != 0 || (a.N * a.OH * a.OW) % 64 != 0 || a.OH > 32) return false;
+  if (a.OW < 1 || (a.N * a.OH * a.OW) % 64 != 0) return false;
+  if (64 % a.OW != 0 || a.OH > 32) return wgrad128_flat_period(a) > 0;
   return a.Hi == a.stride * a.OH;
 }
 
@@ -1751,17 +1782,34 @@ hipError_t launch_conv_wgrad128(const WgradArgs& a, hipStream_t s) {
   L.period = a.OH / g;
   L.a_step = (long long)64 * a.Co * 2;
   L.b_step = (long long)d_oh_full * a.stride * a.Wi * a.Cx * 2;
+  L.step_w = 0;
+  const bool flat = 64 % a.OW != 0 || a.OH > 32;   // conv_wgrad128_applies has checked that the flat form applies then
   static const bool four_waves = getenv("FDG_WGRAD_4W") != nullptr;   // A/B switch for measurements
-  if (!four_waves) {
+  if (flat) {
+    L.period = wgrad128_flat_period(a);
+    if (L.period <= 0) return hipErrorInvalidValue;
+    L.d_oh = d_oh_full % a.OH;
+    L.step_w = 64 % a.OW;
+    L.b_step = (long long)64 * a.Cx * 2;
+    static bool configured_flat = false;
+    if (!configured_flat) {
+      hipError_t e8 = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad128w8_kernel<STAGES, true>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e8 != hipSuccess) return e8;
+      configured_flat = true;
+    }
+    note_kernel("conv_wgrad128w8_kernel<5, flat>");
+    hipLaunchKernelGGL((conv_wgrad128w8_kernel<STAGES, true>), dim3(tiles * L.splits), dim3(512), lds, s, a, L);
+  } else if (!four_waves) {
     static bool configured8 = false;
     if (!configured8) {
-      hipError_t e8 = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad128w8_kernel<STAGES>),
+      hipError_t e8 = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad128w8_kernel<STAGES, false>),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (e8 != hipSuccess) return e8;
       configured8 = true;
     }
     note_kernel("conv_wgrad128w8_kernel<5>");
-    hipLaunchKernelGGL((conv_wgrad128w8_kernel<STAGES>), dim3(tiles * L.splits), dim3(512), lds, s, a, L);
+    hipLaunchKernelGGL((conv_wgrad128w8_kernel<STAGES, false>), dim3(tiles * L.splits), dim3(512), lds, s, a, L);
   } else {
   note_kernel("conv_wgrad128_kernel<5>");
   hipLaunchKernelGGL((conv_wgrad128_kernel<STAGES>), dim3(tiles * L.splits), dim3(256), lds, s, a, L);

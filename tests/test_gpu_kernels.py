@@ -103,6 +103,11 @@ CONV_CASES = [  # n, h, w, ci, co, ksize, stride
     (4, 14, 14, 256, 256, 3, 1),
     (16, 14, 14, 256, 128, 1, 1),   # pixels a multiple of 64, width not a divisor of 64: the weight gradient sees rows of 32
     (16, 14, 14, 128, 256, 1, 1),
+    # 3x3 at widths that do not divide 64 (and a 64-row image): the weight gradient's flat form
+    (16, 14, 14, 128, 256, 3, 1),
+    (64, 7, 7, 128, 128, 3, 1),
+    (1, 64, 64, 128, 128, 3, 1),
+    (48, 6, 10, 128, 128, 3, 1),
 ]
 
 
