@@ -83,8 +83,13 @@ def test_invalid_descriptors_are_rejected():
                 ModuleSpec(2, 16, 8, 8, [Layer(W.BASIC_POSTACT, 16, 16, 1)], delay=-1),
                 ModuleSpec(2, 16, 8, 8, [Layer(W.HEAD_POSTACT, 16), Layer(W.BASIC_POSTACT, 16, 16, 1)]),  # head not last
                 ModuleSpec(2, 16, 8, 8, [Layer(W.BASIC_POSTACT, 16, 12, 1)]),         # channels not a multiple of 8
-                ModuleSpec(0, 16, 8, 8, [Layer(W.BASIC_POSTACT, 16, 16, 1)])):
+                ModuleSpec(0, 16, 8, 8, [Layer(W.BASIC_POSTACT, 16, 16, 1)]),
+                ModuleSpec(2, 16, 8, 8, [Layer(W.BOTTLENECK_POSTACT, 16, 48, 1)]),    # a quarter of 48 is not a multiple of 8
+                ModuleSpec(2, 16, 8, 8, [Layer(6, 16, 16, 1)])):                      # no such layer kind
         assert binding.fdg_module_workspace_bytes(bad) == 0
+    bottleneck = ModuleSpec(2, 16, 8, 8, [Layer(W.BOTTLENECK_POSTACT, 16, 64, 2), Layer(W.BOTTLENECK_POSTACT, 64, 64, 1)])
+    plain = ModuleSpec(2, 16, 8, 8, [Layer(W.BOTTLENECK_POSTACT, 16, 64, 2)])
+    assert binding.fdg_module_workspace_bytes(bottleneck) > binding.fdg_module_workspace_bytes(plain) > 0
     lib = binding.load()
     assert lib.fdg_module_workspace_bytes(None) == 0
     out = ctypes.c_void_p()
