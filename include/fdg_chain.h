@@ -7,7 +7,7 @@
  *       received at the end of the previous iteration, and the update (Eq. 11) -- if one was received;
  *   (2) the forward on the input it received at the end of the previous iteration (module 0: batch t)
  *       -- if one was received;
- * and "right before the iteration ends" (Section III-A, communication; Fig. 1(a)) its output goes to
+ * and, as the last thing an iteration does (Section III-A, communication; Fig. 1(a)), its output goes to
  * module k+1 and the gradient of its input to module k-1.  The last module ends in the loss: it
  * forwards its input, back-propagates the loss gradient of that same batch and updates (delay 0,
  * not shrunk: Section III-B).  So module k (counted from 1) forwards batch t-k+1 and back-propagates

@@ -43,7 +43,7 @@ is the arithmetic.
 
 OracleChain runs K such workers as Algorithm I does: every iteration each module back-propagates the
 oldest saved batch with the gradient it received, updates, forwards the input it received, and the
-tensors are exchanged "right before the iteration ends" (Section III-A, "communication"; Fig. 1(a)).
+tensors are exchanged once per iteration, after all compute of that iteration (Section III-A, "communication"; Fig. 1(a)).
 
 Parity status: every function of this oracle is pinned by tests/test_oracle_*.py (finite
 differences in float64, torch-CPU autograd as an independent library, closed forms, adjoint
@@ -625,7 +625,7 @@ def fdg_schedule(K: int, T: int):
                 assert saved[k][0] == gb, "gradients must arrive in forward order"
                 saved[k].popleft()
                 send_grad[k - 1] = gb
-        # communication: right before the iteration ends
+        # communication: the last thing an iteration does
         for k in range(1, K + 2):
             inbox_act[k] = send_act.get(k)
         for k in range(0, K + 1):
@@ -703,7 +703,7 @@ class OracleChain:
                     b, z = inp
                     send_act[k + 1] = (b, m.forward(z))
                     self.fwd_batch[k] = b
-        # communication, right before the iteration ends
+        # communication, the last thing an iteration does
         self.inbox_act = [send_act.get(k) for k in range(K)]
         self.inbox_grad = [send_grad.get(k) for k in range(K)]
         return result
