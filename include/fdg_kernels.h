@@ -55,7 +55,9 @@ int fdgk_conv_dgrad_gates(int n, int h, int w, int ci, int co, int ksize, int st
 /* The same for the last data gradient of a block, whose fp32 result plus the shortcut gradient (addend, counted where
  * addmask > 0) is the gradient at the output of the layer BELOW: gate_b16 = that layer's output, bnx_b16 = the input
  * of that layer's last batch norm, and the two sums are taken from the fp32 values (dx_f32 is required; it is what
- * that batch norm's backward reads).  Narrow layers only (16 / 32 / 64 channels in and out, 3x3, stride 1); 1 elsewhere. */
+ * that batch norm's backward reads).  Where a kernel's output stage sums the fp32 values: narrow layers (16 / 32 / 64
+ * channels in and out, 3x3, stride 1) and 1x1 unit-stride layers that the two-workgroup form of the wide gather kernel
+ * runs (input channels a multiple of 64, at most 1024 output channels of the convolution, 300 tiles or more); 1 elsewhere. */
 int fdgk_conv_dgrad_feeding_next(const void* dy_b16, const void* wt_b16, const float* addend_f32, const void* addmask_b16,
                                  const void* gate_b16, const void* bnx_b16, float* gsums_f32, float* dx_f32, void* dx_b16,
                                  int n, int h, int w, int ci, int co, int ksize, int stride, void* hip_stream);

@@ -141,7 +141,9 @@ constexpr int stats_stage_bytes(int BN) { return 4 * ((BN / 4) % 16 == 0 ? 1 : (
 // Kernels with eight waves (256 registers, 8 regions in the LDS) turn the block ROWS = 16 pixels at a time, issue the
 // loads of GROUP = 5 iterations together (about 14 registers per iteration) and park the statistics of PARKW = 8
 // waves where the regions were (stats_lds may then overlap them: a barrier separates the two uses).
-template <int FN, int BN, int GROUP = 10, int ROWS = 32, int PARKW = 4>
+// F32S: the per-channel sums are of the fp32 values (a data gradient whose fp32 result the batch norm below reads),
+// not of their bf16 roundings.
+template <int FN, int BN, int GROUP = 10, int ROWS = 32, int PARKW = 4, bool F32S = false>
 __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x16 (&acc)[FN], int m_base, int c_tile,
                                              int lane, unsigned char* lds, unsigned char* stats_lds) {
   static_assert(FN * 32 == BN, "one wave carries all channels of the tile");
@@ -259,7 +261,8 @@ __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x
         if (p_f32) *(gf4)(p_f32 + 4 * o[k]) = v[k];
         if (p_b16) *(gu2)(p_b16 + 2 * o[k]) = packed;
         if (want_stats) {
-          const float r0 = bf16_lo(packed[0]), r1 = bf16_hi(packed[0]), r2 = bf16_lo(packed[1]), r3 = bf16_hi(packed[1]);
+          const float r0 = F32S ? v[k][0] : bf16_lo(packed[0]), r1 = F32S ? v[k][1] : bf16_hi(packed[0]);
+          const float r2 = F32S ? v[k][2] : bf16_lo(packed[1]), r3 = F32S ? v[k][3] : bf16_hi(packed[1]);
           const int kk = (it0 + k) % PERIOD;
           s1[kk][0] += r0; s1[kk][1] += r1; s1[kk][2] += r2; s1[kk][3] += r3;
           if (p_bnx) {
@@ -311,7 +314,7 @@ __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x
 // 32-pixel block (wave wk keeps block j = wk and receives its partner's), then all four run the output stage.
 // smem must hold max(4 * FN * 16 * 256, 4 * out_stage_bytes(BN) + stats_stage_bytes(BN)) bytes and be idle (no loads
 // in flight).
-template <int FN, int BN>
+template <int FN, int BN, bool F32S = false>
 __device__ __forceinline__ void combine_and_store32(const GatherConvArgs& a, f32x16 (&acc)[FN][2], int m_tile, int c_tile,
                                                     int wave_m, int wk, int lane, unsigned char* smem) {
   __syncthreads();
@@ -336,7 +339,7 @@ __device__ __forceinline__ void combine_and_store32(const GatherConvArgs& a, f32
     }
   __syncthreads();
   const int wave = wave_m * 2 + wk;
-  store_rows32<FN, BN>(a, keep, m_tile + wave_m * 64 + wk * 32, c_tile, lane, smem + (size_t)wave * out_stage_bytes(BN),
+  store_rows32<FN, BN, 10, 32, 4, F32S>(a, keep, m_tile + wave_m * 64 + wk * 32, c_tile, lane, smem + (size_t)wave * out_stage_bytes(BN),
                        smem + (size_t)4 * out_stage_bytes(BN));
 }
 
@@ -381,6 +384,7 @@ __device__ __forceinline__ void combine8_and_store32(const GatherConvArgs& a, f3
 
 // The wide-channel kernel (conv_wide_kernels.hip): input channels a multiple of 64.
 bool conv_gather_wide_applies(const GatherConvArgs& a);
+bool conv_gather_pair_applies(const GatherConvArgs& a);   // the two-workgroup form of the wide gather kernel runs it
 hipError_t launch_conv_gather_wide(const GatherConvArgs& a, hipStream_t s);
 // The wide-channel weight gradient: output and input channels multiples of 160, output width dividing 64.
 bool conv_wgrad_wide_applies(const WgradArgs& a);

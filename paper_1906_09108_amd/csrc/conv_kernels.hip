@@ -388,15 +388,20 @@ hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, co
   return conv_dgrad_impl(c, dy, wt, addend, addmask, nullptr, nullptr, nullptr, out_f32, out_b16, s);
 }
 
-// the narrow kernel runs the whole data gradient of this layer
+// the narrow kernel, or the two-workgroup form of the wide gather kernel (1x1 layers), runs the whole data gradient of
+// this layer: their output stages take the sums of the fp32 values
 bool conv_dgrad_feeds_next(const ConvShape& c) {
-  if (c.stride != 1 || c.T != 9) return false;
+  if (c.stride != 1 || (c.T != 9 && c.T != 1)) return false;
   GatherConvArgs a{};
   a.N = c.N; a.Hi = c.Ho(); a.Wi = c.Wo(); a.Ci = c.Co; a.Co = c.Cip; a.w_rows = c.Cip; a.Kw = c.T * c.Co;
-  a.OH = c.Hi; a.OW = c.Wi; a.OHf = c.Hi; a.OWf = c.Wi; a.in_stride = 1; a.out_stride = 1; a.ntaps = 9;
-  for (int r = 0; r < 3; ++r)
-    for (int q = 0; q < 3; ++q) a.tap[r * 3 + q] = pack_tap(1 - r, 1 - q, r * 3 + q);
-  return conv_narrow_applies(a);
+  a.OH = c.Hi; a.OW = c.Wi; a.OHf = c.Hi; a.OWf = c.Wi; a.in_stride = 1; a.out_stride = 1; a.ntaps = c.T;
+  if (c.T == 9) {
+    for (int r = 0; r < 3; ++r)
+      for (int q = 0; q < 3; ++q) a.tap[r * 3 + q] = pack_tap(1 - r, 1 - q, r * 3 + q);
+    return conv_narrow_applies(a);
+  }
+  a.tap[0] = pack_tap(0, 0, 0);
+  return conv_gather_pair_applies(a);
 }
 
 hipError_t conv_dgrad_feeding_next(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,

@@ -54,7 +54,7 @@ constexpr size_t gather_dma_lds_bytes(int BN, int STAGES) {
   return need;
 }
 
-template <int BN, int STAGES, bool KTAIL>
+template <int BN, int STAGES, bool KTAIL, bool F32S = false>
 __device__ __forceinline__ void gather_dma_body(const GatherConvArgs& a, int m_tiles, int n_tiles) {
   constexpr int BM = 128;
   static_assert(BN % 32 == 0, "whole 32x32 blocks");
@@ -183,7 +183,7 @@ __device__ __forceinline__ void gather_dma_body(const GatherConvArgs& a, int m_t
     }
   }
   wait_vmcnt<0>();
-  combine_and_store32<FN, BN>(b, acc, m0, c0, wave_m, wk, lane, smem);
+  combine_and_store32<FN, BN, F32S>(b, acc, m0, c0, wave_m, wk, lane, smem);
 }
 
 template <int BN, int STAGES, bool KTAIL>
@@ -191,10 +191,11 @@ __global__ __launch_bounds__(256) void conv_gather_dma_kernel(GatherConvArgs a, 
   gather_dma_body<BN, STAGES, KTAIL>(a, m_tiles, n_tiles);
 }
 // The same within 256 registers, so that two workgroups (two waves per SIMD) fit a compute unit: for the two-stage form.
-template <int BN, int STAGES, bool KTAIL>
+// F32S: sums of the fp32 values in the output stage (GatherConvArgs::stats_f32), for a data gradient that feeds the layer below.
+template <int BN, int STAGES, bool KTAIL, bool F32S>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void conv_gather_dma_pair_kernel(
     GatherConvArgs a, int m_tiles, int n_tiles) {
-  gather_dma_body<BN, STAGES, KTAIL>(a, m_tiles, n_tiles);
+  gather_dma_body<BN, STAGES, KTAIL, F32S>(a, m_tiles, n_tiles);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -924,21 +925,37 @@ static hipError_t run_wide_k(const GatherConvArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-static hipError_t run_wide_pair(const GatherConvArgs& a, hipStream_t s) {
+template <bool F32S>
+static hipError_t run_wide_pair_f(const GatherConvArgs& a, hipStream_t s) {
   constexpr int BN = 128, STAGES = 2;
   constexpr size_t lds = gather_dma_lds_bytes(BN, STAGES);
   static_assert(2 * lds <= 160 * 1024, "two workgroups in the LDS of one compute unit");
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_gather_dma_pair_kernel<BN, STAGES, false>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_gather_dma_pair_kernel<BN, STAGES, false, F32S>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     configured = true;
   }
-  note_kernel("conv_gather_dma_pair_kernel<128, 2>");
+  note_kernel(F32S ? "conv_gather_dma_pair_kernel<128, 2, feeding>" : "conv_gather_dma_pair_kernel<128, 2>");
   const int m_tiles = (a.N * a.OH * a.OW + 127) / 128, n_tiles = (a.Co + BN - 1) / BN;
-  hipLaunchKernelGGL((conv_gather_dma_pair_kernel<BN, STAGES, false>), dim3(m_tiles * n_tiles), dim3(256), lds, s, a, m_tiles, n_tiles);
+  hipLaunchKernelGGL((conv_gather_dma_pair_kernel<BN, STAGES, false, F32S>), dim3(m_tiles * n_tiles), dim3(256), lds, s, a, m_tiles, n_tiles);
   return hipGetLastError();
+}
+static hipError_t run_wide_pair(const GatherConvArgs& a, hipStream_t s) {
+  return (a.stats && a.stats_f32) ? run_wide_pair_f<true>(a, s) : run_wide_pair_f<false>(a, s);
+}
+
+// The two-workgroup form runs this layer (and with it the output stage that can take the sums of the fp32 values).
+bool conv_gather_pair_applies(const GatherConvArgs& a) {
+  static const bool no_patch = getenv("FDG_NO_PATCH") != nullptr;
+  if (a.nclass > 1 || a.Co % 160 == 0 || a.Ci % 64 != 0 || !conv_gather_wide_applies(a) || (conv_patch_applies(a) && !no_patch)) return false;
+  const int steps = a.ntaps * ((a.Ci + 63) / 64);
+  const long tiles = (long)((a.N * a.OH * a.OW + 127) / 128) * ((a.Co + 127) / 128);
+  static const bool no_short = getenv("FDG_NO_SHORT_K") != nullptr;   // A/B switch for measurements
+  static const int pair_steps = getenv("FDG_PAIR_STEPS") ? atoi(getenv("FDG_PAIR_STEPS")) : 16;     // for measurements
+  static const int pair_tiles = getenv("FDG_PAIR_TILES") ? atoi(getenv("FDG_PAIR_TILES")) : 300;
+  return !no_short && steps <= pair_steps && tiles >= pair_tiles;
 }
 
 template <int BN, int STAGES>
@@ -952,18 +969,14 @@ hipError_t launch_conv_gather_wide(const GatherConvArgs& a, hipStream_t s) {
     return a.Co % 160 == 0 ? run_wide<160, 4>(a, s) : run_wide<128, 4>(a, s);
   }
   if (!conv_gather_wide_applies(a) || a.N * a.OH * a.OW <= 0) return hipErrorInvalidValue;
+  if (a.stats && a.stats_f32 && !conv_gather_pair_applies(a)) return hipErrorInvalidValue;   // only that form takes the sums of the fp32 values
   static const bool no_patch = getenv("FDG_NO_PATCH") != nullptr;
   if (conv_patch_applies(a) && !no_patch) return a.Co % 160 == 0 ? run_patch_rows<160>(a, s) : run_patch_rows<128>(a, s);
-  if (a.Co % 160 == 0) return run_wide<160, 4>(a, s);
   // A short contraction (a 1x1 convolution: at most 16 steps per tile) over more tiles than compute units: two stages
   // instead of four are 75 KB of LDS, so two workgroups share a compute unit, one's output stage runs beside the
   // other's loads and main loop, and 257 .. 512 tiles take one round instead of two.
-  const int steps = a.ntaps * ((a.Ci + 63) / 64);
-  const long tiles = (long)((a.N * a.OH * a.OW + 127) / 128) * ((a.Co + 127) / 128);
-  static const bool no_short = getenv("FDG_NO_SHORT_K") != nullptr;   // A/B switch for measurements
-  static const int pair_steps = getenv("FDG_PAIR_STEPS") ? atoi(getenv("FDG_PAIR_STEPS")) : 16;     // for measurements
-  static const int pair_tiles = getenv("FDG_PAIR_TILES") ? atoi(getenv("FDG_PAIR_TILES")) : 300;
-  if (!no_short && a.nclass <= 1 && steps <= pair_steps && tiles >= pair_tiles && a.Ci % 64 == 0) return run_wide_pair(a, s);
+  if (conv_gather_pair_applies(a)) return run_wide_pair(a, s);
+  if (a.Co % 160 == 0) return run_wide<160, 4>(a, s);
   return run_wide<128, 4>(a, s);
 }
 

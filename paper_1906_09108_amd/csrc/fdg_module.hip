@@ -657,6 +657,19 @@ hipError_t dgrad_relu_bn_backward(const fdg_module* m, const SlotView& v, const 
   return bn_backward(m, v, b, g, false, gate, x, bn_addend, out_f32, out_b16, s);
 }
 
+// The last batch norm of a layer that ends in batch norm + ReLU, and the input of that batch norm in slot v (nullptr:
+// the layer does not end that way).
+const BnInfo* closing_bn(const Plan& p, const SlotView& v, const LayerPlan& L, const bf16_t** bnx) {
+  int bn = -1;
+  size_t x = 0;
+  if (L.kind == FDG_STEM_CONV_BN_RELU) { bn = L.bn[0]; x = L.act[0]; }
+  else if (L.kind == FDG_BASIC_POSTACT) { bn = L.bn[1]; x = L.act[2]; }
+  else if (L.kind == FDG_BOTTLENECK_POSTACT) { bn = L.bn[3]; x = L.act[5]; }
+  if (bn < 0) return nullptr;
+  *bnx = v.act(x);
+  return &p.bns[bn];
+}
+
 // The layers of the module on x (fp32 NCHW) with the weights of slot v, every intermediate the backward needs
 // written where v keeps them.  `replayed`: this forward ran before (v's snapshot and labels are in place); running
 // statistics stay as they are and y_dev may be NULL (a head then needs it as scratch for loss and logits).
@@ -870,7 +883,7 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
   int cur = 0;
   if (!p.is_top)  // gradient shrinking of Eq. 15: multiply by beta before anything else
     FDG_TRY(launch_nchw_to_nhwc(grad_out_dev, m->G(cur), m->GB(cur), N, p.out_c, p.out_h * p.out_w, p.out_c, p.d.beta, s));
-  static const bool no_feed = getenv("FDG_NO_GATED_DGRAD") != nullptr;   // A/B switch for measurements
+  static const bool no_feed = getenv("FDG_NO_GATED_DGRAD") != nullptr || getenv("FDG_NO_FEED") != nullptr;   // A/B switches for measurements
   bool fed = false;   // G(cur) came from the layer above already gated by this layer's output, with this layer's
                       // last batch norm's two sums in bsums
   for (int li = (int)p.L.size() - 1; li >= 0; --li) {
@@ -923,11 +936,9 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
         // identity shortcut: the masked incoming gradient joins the branch gradient.  Where the narrow kernel runs
         // and the layer below ends in batch norm + ReLU, its output stage also does the first half of that layer's
         // backward: the ReLU gate and the two sums of the batch norm.
-        const LayerPlan* below = li > 0 ? &p.L[li - 1] : nullptr;
-        const bool below_ok = below && (below->kind == FDG_BASIC_POSTACT || below->kind == FDG_STEM_CONV_BN_RELU);
-        const BnInfo* bb = below_ok ? &p.bns[below->kind == FDG_BASIC_POSTACT ? below->bn[1] : below->bn[0]] : nullptr;
+        const bf16_t* bnx = nullptr;
+        const BnInfo* bb = li > 0 ? closing_bn(p, v, p.L[li - 1], &bnx) : nullptr;
         if (!no_feed && bb && bb->C == c1.sh.Cip && conv_dgrad_feeds_next(c1.sh)) {
-          const bf16_t* bnx = v.act(below->kind == FDG_BASIC_POSTACT ? below->act[2] : below->act[0]);
           FDG_TRY(side_wait_readers(m, m->GB(nxt), s));
           const double bytes = 2 * conv_out_elems(c1.sh) + 2 * conv_w_elems(c1.sh) + conv_in_elems(c1.sh) * (4 + 2 + 2 + 2 + 4 + 2);
           ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c1.sh), bytes, s);
@@ -946,7 +957,8 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
       const bf16_t *t_c1 = v.act(L.act[0]), *t_a1 = v.act(L.act[1]), *t_c2 = v.act(L.act[2]), *t_a2 = v.act(L.act[4]),
                    *t_c3 = v.act(L.act[5]), *t_y = v.act(L.out_b);
       // final ReLU mask (y > 0) then BN3; then twice: weight gradient, data gradient through ReLU and batch norm
-      FDG_TRY(bn_backward(m, v, b3, m->G(cur), true, t_y, t_c3, nullptr, nullptr, m->T(0), s));
+      if (fed_here) FDG_TRY(bn_backward_fed_from_above(m, v, b3, m->G(cur), t_c3, m->T(0), s));
+      else FDG_TRY(bn_backward(m, v, b3, m->G(cur), true, t_y, t_c3, nullptr, nullptr, m->T(0), s));
       FDG_TRY(mconv_wgrad(m, c3, t_a2, m->T(0), s));
       FDG_TRY(dgrad_relu_bn_backward(m, v, c3, m->T(0), v.Wt(c3), nullptr, b2, t_a2, t_c2, m->T(1), nullptr, nullptr, m->T(0), s));
       FDG_TRY(mconv_wgrad(m, c2, t_a1, m->T(0), s));
@@ -962,7 +974,22 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
           FDG_TRY(mconv_dgrad(m, c1, m->T(0), v.Wt(c1), m->TPB(), nullptr, m->G(nxt), m->GB(nxt), s));
         }
       } else if (need_dx) {
-        FDG_TRY(mconv_dgrad(m, c1, m->T(0), v.Wt(c1), m->G(cur), t_y, m->G(nxt), m->GB(nxt), s));
+        // identity shortcut: as in the basic block, the data gradient that ends this block's backward can also gate by
+        // the output of the layer below and take the two sums of that layer's last batch norm
+        const bf16_t* bnx = nullptr;
+        const BnInfo* bb = li > 0 ? closing_bn(p, v, p.L[li - 1], &bnx) : nullptr;
+        if (!no_feed && bb && bb->C == c1.sh.Cip && conv_dgrad_feeds_next(c1.sh)) {
+          FDG_TRY(side_wait_readers(m, m->GB(nxt), s));
+          const double bytes = 2 * conv_out_elems(c1.sh) + 2 * conv_w_elems(c1.sh) + conv_in_elems(c1.sh) * (4 + 2 + 2 + 2 + 4 + 2);
+          ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c1.sh), bytes, s);
+          const hipError_t e = conv_dgrad_feeding_next(c1.sh, m->T(0), v.Wt(c1), m->G(cur), t_y, in_b, bnx,
+                                                       m->bsums() + bb->stat_off, m->G(nxt), m->GB(nxt), s, p.stat_rep);
+          ps.label(c1.sh);
+          FDG_TRY(e);
+          fed = true;
+        } else {
+          FDG_TRY(mconv_dgrad(m, c1, m->T(0), v.Wt(c1), m->G(cur), t_y, m->G(nxt), m->GB(nxt), s));
+        }
       }
     } else {  // pre-activation block: y = conv2(o2) + shortcut
       const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]];

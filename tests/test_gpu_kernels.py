@@ -258,7 +258,8 @@ def test_gated_data_gradient_feeds_the_batch_norm_backward(case):
 
 
 @pytest.mark.parametrize("case", [(3, 7, 5, 16, 16, 3, 1), (16, 32, 32, 16, 16, 3, 1), (4, 16, 16, 32, 32, 3, 1), (3, 8, 8, 64, 64, 3, 1),
-                                  (9, 64, 64, 64, 64, 3, 1)])
+                                  (9, 64, 64, 64, 64, 3, 1),
+                                  (25, 14, 14, 1024, 256, 1, 1)])   # 1x1 of a bottleneck block: the two-workgroup wide kernel
 def test_data_gradient_that_feeds_the_layer_below(case):
     """conv_dgrad_feeding_next: g = gate > 0 ? dgrad + addend * [addmask > 0] : 0 in fp32 (and its bf16 copy), and the
     sums [sum g, sum g * x] of the FP32 values.  Reference: the oracle's data gradient, gate and mask applied in numpy."""
@@ -268,7 +269,7 @@ def test_data_gradient_that_feeds_the_layer_below(case):
     print("dgrad feeding next", case, flush=True)
     x_unused, wt, dy, ho, wo = _conv_data(case, 21)
     r = np.random.default_rng(22)
-    ref = K32.conv_bwd_data(dy, wt, x_unused.shape, s, 1).astype(np.float64)
+    ref = K32.conv_bwd_data(dy, wt, x_unused.shape, s, 1 if k == 3 else 0).astype(np.float64)
     add = r.standard_normal(ref.shape).astype(np.float32) * 0.5
     mask = bf16_round(np.maximum(r.standard_normal(ref.shape), 0))
     gate = bf16_round(np.maximum(r.standard_normal(ref.shape), 0))
