@@ -151,7 +151,7 @@ def test_conv_weight_gradient_on_sampled_channels(case):
     assert rel(got, ref) <= F32_TOL
 
 
-@pytest.mark.parametrize("m,c", [(128 * 8 * 8, 640), (128 * 16 * 16, 320), (128 * 32 * 32, 16), (128 * 64 * 64, 64)])
+@pytest.mark.parametrize("m,c", [(128 * 8 * 8, 640), (128 * 16 * 16, 320), (128 * 32 * 32, 16), (128 * 64 * 64, 64), (128 * 14 * 14, 1024), (128 * 14 * 14, 256)])
 def test_batch_norm_on_sampled_channels(m, c):
     from paper_1906_09108_amd import kernels as K
     t = _t()
