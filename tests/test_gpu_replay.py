@@ -54,7 +54,7 @@ def test_replay_backward_first_order_of_algorithm_1():
     _check(spec, steps=3, strict=False, seed=2, backward_first=True)
 
 
-@pytest.mark.parametrize("idx,n,steps", [(3, 16, 2), (4, 8, 1), (5, 8, 1)])
+@pytest.mark.parametrize("idx,n,steps", [(3, 16, 2), (4, 8, 1), (5, 8, 1), (8, 25, 1)])
 def test_replay_configs_reduced_batch(idx, n, steps):
     spec = W.config(idx, n=n)
     print(f"replay case cfg{idx} n={n}", flush=True)
