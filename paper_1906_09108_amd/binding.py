@@ -159,11 +159,41 @@ def fdg_module_create_ex(spec, save_mode: int, workspace, stream=None) -> int:
     return out.value
 
 
+def _shape(handle: int, which: str) -> Tuple[int, int, int, int]:
+    shp = (ctypes.c_int32 * 4)()
+    getattr(load(), which)(handle, ctypes.byref(shp))
+    return tuple(int(v) for v in shp)
+
+
+def _dense(t, dtype_name: str, numel: int) -> bool:
+    """The library reads raw pointers: a tensor handed to it must be what the header says it is (device memory,
+    dense, of the stated element type and size), or the kernels would read out of bounds."""
+    import torch
+    return (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.dtype == getattr(torch, dtype_name)
+            and t.numel() == numel)
+
+
 def fdg_forward(handle: int, x, labels, y, stream=None) -> int:
+    """FDG_ERR_INVALID_ARG without calling the library if a tensor is not a dense CUDA tensor of the type and size
+    include/fdg.h states (x, y: float32; labels: int32 [n])."""
+    n, c, h, w = _shape(handle, "fdg_input_shape")
+    on, oc, oh, ow = _shape(handle, "fdg_output_shape")
+    if x is None or y is None or not _dense(x, "float32", n * c * h * w) or not _dense(y, "float32", on * oc * oh * ow):
+        return FDG_ERR_INVALID_ARG
+    if labels is not None and not _dense(labels, "int32", n):
+        return FDG_ERR_INVALID_ARG
     return int(load().fdg_forward(handle, _ptr(x), _ptr(labels), _ptr(y), _stream_handle(stream)))
 
 
 def fdg_backward_delayed(handle: int, grad_out, grad_in, stream=None) -> int:
+    """FDG_ERR_INVALID_ARG without calling the library if a tensor is not a dense float32 CUDA tensor of the forward's
+    output (grad_out) or input (grad_in) size."""
+    n, c, h, w = _shape(handle, "fdg_input_shape")
+    on, oc, oh, ow = _shape(handle, "fdg_output_shape")
+    if grad_out is not None and not _dense(grad_out, "float32", on * oc * oh * ow):
+        return FDG_ERR_INVALID_ARG
+    if grad_in is not None and not _dense(grad_in, "float32", n * c * h * w):
+        return FDG_ERR_INVALID_ARG
     return int(load().fdg_backward_delayed(handle, _ptr(grad_out), _ptr(grad_in), _stream_handle(stream)))
 
 
@@ -321,6 +351,9 @@ class FdgChain:
     def step(self, x, labels, lr: float, stream=None) -> int:
         """One iteration on batch (x, labels), both CUDA tensors.  Returns the 1-based batch whose loss and logits
         are now being written to self.top_y (0 while the last module idles)."""
+        n, c, h, w = _shape(self.modules[0].handle, "fdg_input_shape")
+        if not _dense(x, "float32", n * c * h * w) or not _dense(labels, "int32", n):
+            raise FdgError(FDG_ERR_INVALID_ARG, "fdg_chain_step (x: dense float32 CUDA [n,c,h,w]; labels: int32 CUDA [n])")
         b = ctypes.c_int32()
         st = load().fdg_chain_step(self.handle, _ptr(x), _ptr(labels), float(lr), _ptr(self.top_y), ctypes.byref(b),
                                    _stream_handle(stream))
