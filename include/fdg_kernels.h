@@ -94,6 +94,19 @@ int fdgk_bn_bwd(const void* dy, int dy_is_f32, const void* mask_b16, const void*
                 const float* gamma, float* scratch_f32, const float* addend_f32, float* dx_f32, void* dx_b16,
                 float* dgamma, float* dbeta, int m, int c, float eps, void* hip_stream);
 
+/* fdgk_bn_bwd for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the same computation and the same kernels, but the [2c] sums live in an array
+ * that is part of the library's code object (one copy per GPU, 16 KiB, held until the process ends) instead of a
+ * caller-provided scratch_f32.  The call allocates and frees nothing.  Limit: c <= fdgk_bn_bwd_static_max_c() (2048);
+ * a larger c (or c % 8 != 0, m <= 0, a required pointer NULL) returns 1 (hipErrorInvalidValue) and enqueues nothing.
+ * The array is cleared by a fill kernel on hip_stream at the start of every call and keeps the last call's sums
+ * afterwards.  Every call on one GPU shares that GPU's array: calls that may overlap on one GPU (different streams,
+ * different host threads) race; order them.  The device that owns hip_stream must be the current device.        */
+int fdgk_bn_bwd_static_max_c(void);
+int fdgk_bn_bwd_static(const void* dy, int dy_is_f32, const void* mask_b16, const void* x_b16, const float* sums_f32,
+                       const float* gamma, const float* addend_f32, float* dx_f32, void* dx_b16, float* dgamma, float* dbeta,
+                       int m, int c, float eps, void* hip_stream);
+
 /* The second half of fdgk_bn_bwd for a gradient g_b16 [m, c] that is already gated and whose sums
  * gsums_f32 = [sum g, sum g*x] were left by fdgk_conv_dgrad_gated: dbeta = sum g, dgamma = (sum g*x - mean * sum g) / sqrt(var+eps),
  * dx as in fdgk_bn_bwd.                                                                                */

@@ -3,6 +3,8 @@
 #include "../../include/fdg_kernels.h"
 #include "fdg_internal.h"
 
+#include <mutex>
+
 using namespace fdg;
 
 namespace {
@@ -13,6 +15,36 @@ bool conv_shape(ConvShape& c, int n, int h, int w, int ci, int co, int ksize, in
   return true;
 }
 inline hipStream_t st(void* s) { return static_cast<hipStream_t>(s); }
+
+// ---- the scratch of the entry point that allocates nothing (fdgk_bn_bwd_static) ----
+// One array per GPU, held until the process ends: the two per-channel sums of a batch-norm backward for up to
+// kStaticMaxC channels.  In host code the array's name is only a stand-in; its device address is looked up once per
+// device (with that device current) and that pointer is what kernels, fills and copies are given.
+constexpr int kStaticMaxC = 2048;
+constexpr int kStaticMaxDevices = 64;
+static __device__ __align__(256) float scratch[2 * kStaticMaxC];
+std::mutex g_scratch_lock;
+float* g_scratch_ptr[kStaticMaxDevices] = {};
+
+// the current device's copy of `scratch`, or nullptr with *err set
+float* static_scratch(hipError_t* err) {
+  int dev = -1;
+  *err = hipGetDevice(&dev);
+  if (*err != hipSuccess) return nullptr;
+  if (dev < 0 || dev >= kStaticMaxDevices) { *err = hipErrorInvalidDevice; return nullptr; }
+  std::lock_guard<std::mutex> hold(g_scratch_lock);
+  if (!g_scratch_ptr[dev]) {
+    float* p = nullptr;
+    *err = hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch));
+    if (*err != hipSuccess || !p) {
+      if (*err == hipSuccess) *err = hipErrorInvalidSymbol;
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
 }  // namespace
 
 extern "C" {
@@ -106,6 +138,24 @@ int fdgk_bn_bwd(const void* dy, int dy_is_f32, const void* mask_b16, const void*
   hipError_t e = launch_bn_bwd_reduce(a, st(hip_stream));
   if (e != hipSuccess) return (int)e;
   return (int)launch_bn_bwd_apply(a, st(hip_stream));
+}
+
+int fdgk_bn_bwd_static_max_c(void) { return kStaticMaxC; }
+
+int fdgk_bn_bwd_static(const void* dy, int dy_is_f32, const void* mask_b16, const void* x_b16, const float* sums_f32,
+                       const float* gamma, const float* addend_f32, float* dx_f32, void* dx_b16, float* dgamma, float* dbeta,
+                       int m, int c, float eps, void* hip_stream) {
+  if (!dy || !mask_b16 || !x_b16 || !sums_f32 || !gamma || !dgamma || !dbeta) return (int)hipErrorInvalidValue;
+  if (c <= 0 || c > kStaticMaxC || c % 8 != 0 || m <= 0) return (int)hipErrorInvalidValue;   // beyond the array: refused
+  hipError_t e = hipSuccess;
+  float* sums2 = static_scratch(&e);
+  if (!sums2) return (int)e;
+  // the array keeps the last call's sums: the part this call adds into starts at zero (a fill kernel, so that a
+  // caller may record the call into a graph)
+  e = launch_fill_zero(sums2, (size_t)2 * c * sizeof(float), st(hip_stream));
+  if (e != hipSuccess) return (int)e;
+  return fdgk_bn_bwd(dy, dy_is_f32, mask_b16, x_b16, sums_f32, gamma, sums2, addend_f32, dx_f32, dx_b16, dgamma, dbeta, m, c,
+                     eps, hip_stream);
 }
 
 int fdgk_bn_bwd_gated(const void* g_b16, const void* x_b16, const float* sums_f32, const float* gamma,

@@ -7,7 +7,7 @@ import ctypes
 from .binding import _ptr, _stream_handle, load
 
 KERNEL_EXPORTS = ["fdgk_conv_fwd", "fdgk_conv_dgrad", "fdgk_conv_dgrad_gated", "fdgk_conv_dgrad_feeding_next", "fdgk_conv_dgrad_gates", "fdgk_bn_bwd_gated", "fdgk_conv_wgrad", "fdgk_conv_wgrad_scratch_bytes", "fdgk_bn_stats", "fdgk_bn_apply",
-                  "fdgk_bn_bwd", "fdgk_sgd"]
+                  "fdgk_bn_bwd", "fdgk_sgd", "fdgk_bn_bwd_static", "fdgk_bn_bwd_static_max_c"]
 _ready = False
 
 
@@ -28,6 +28,8 @@ def _lib():
         lib.fdgk_bn_apply.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, f, i, vp]
         lib.fdgk_bn_bwd.argtypes = [vp, i, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, f, vp]
         lib.fdgk_sgd.argtypes = [vp, vp, vp, sz, f, f, f, vp]
+        lib.fdgk_bn_bwd_static.argtypes = [vp, i, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, f, vp]
+        lib.fdgk_bn_bwd_static_max_c.argtypes = []
         for n in KERNEL_EXPORTS:
             if getattr(lib, n).argtypes is None:   # a pointer passed without a declared type would be cut to 32 bits
                 raise RuntimeError(f"{n}: argument types not declared")
@@ -103,6 +105,21 @@ def fdgk_bn_bwd(dy, dy_is_f32, mask_b16, x_b16, sums_f32, gamma, scratch_f32, ad
     _ok(_lib().fdgk_bn_bwd(_ptr(dy), int(dy_is_f32), _ptr(mask_b16), _ptr(x_b16), _ptr(sums_f32), _ptr(gamma),
                            _ptr(scratch_f32), _ptr(addend_f32), _ptr(dx_f32), _ptr(dx_b16), _ptr(dgamma), _ptr(dbeta),
                            m, c, eps, _stream_handle(stream)), "fdgk_bn_bwd")
+
+
+def fdgk_bn_bwd_static_max_c() -> int:
+    return int(_lib().fdgk_bn_bwd_static_max_c())
+
+
+def fdgk_bn_bwd_static(dy, dy_is_f32, mask_b16, x_b16, sums_f32, gamma, addend_f32, dx_f32, dx_b16, dgamma, dbeta, m, c, eps,
+                       stream=None, check=True) -> int:
+    """fdgk_bn_bwd without a scratch argument: the sums live in the library's own per-GPU array."""
+    rc = int(_lib().fdgk_bn_bwd_static(_ptr(dy), int(dy_is_f32), _ptr(mask_b16), _ptr(x_b16), _ptr(sums_f32), _ptr(gamma),
+                                       _ptr(addend_f32), _ptr(dx_f32), _ptr(dx_b16), _ptr(dgamma), _ptr(dbeta), m, c, eps,
+                                       _stream_handle(stream)))
+    if check:
+        _ok(rc, "fdgk_bn_bwd_static")
+    return rc
 
 
 def fdgk_sgd(theta, v, g, count, lr, mu, wd, stream=None):
