@@ -198,7 +198,47 @@ fdg_status fdg_module_traits(const fdg_module* m, int32_t* delay, int32_t* is_bo
 fdg_status fdg_queue_state(const fdg_module* m, int32_t* outstanding, int64_t* oldest_seq,
                            int64_t* newest_seq);
 
-/* Per-kernel timing, for measurement only.  While enabled, every launch group of a call is bracketed by
+/* ---- parity accessors: the tensors inside a step, layer by layer ------------------------------------------
+ * Eq. 8 / Eq. 9 / Eq. 10 are a chain over the layers of a module; these accessors expose every link of that chain
+ * so that each layer of a real step can be checked by itself: given the input the layer actually saw, did it produce
+ * the output, the input gradient and the parameter gradient its definition gives?  All results are HOST fp32,
+ * NCHW, dense, with the padding channels of the internal layout dropped; bf16 tensors are widened exactly.  Every
+ * call synchronises the module's streams.  `shape` (optional) receives n, c, h, w; `count` must be n*c*h*w.
+ *
+ * fdg_saved_read: a tensor of the saved forward with sequence number `seq` (it must still be in the ring:
+ * newest_seq - delay <= seq <= newest_seq; a context stays readable after its backward until a forward reuses its
+ * slot).  Not available with FDG_SAVE_INPUT_AND_REPLAY before the backward of that context has replayed it.
+ *   which 0..5 : the layer's saved intermediates (bf16), by layer kind
+ *        STEM               0 = conv output
+ *        BASIC_POSTACT      0 = conv1 output, 1 = relu(bn1), 2 = conv2 output, 3 = projection output (if projecting)
+ *        BASIC_PREACT       0 = relu(bn1(x)), 1 = conv1 output, 2 = relu(bn2)
+ *        BOTTLENECK_POSTACT 0 = conv1 output, 1 = relu(bn1), 2 = conv2 output, 3 = projection output, 4 = relu(bn2),
+ *                           5 = conv3 output
+ *        HEAD_PREACT        0 = relu(bn(x))
+ *   which 6    : the bf16 copy of the layer's output (the next layer's operand and ReLU gate); not for heads
+ *   which 7    : the bf16 copy of the layer's input
+ *   which 8    : heads: the pooled features [n, c, 1, 1] (fp32)
+ *   which 9    : heads: d loss / d logits [n, classes, 1, 1] (fp32)
+ * FDG_ERR_INVALID_ARG for a tensor the layer does not have, a seq outside the ring, or a wrong count.
+ *
+ * fdg_trace_*: the fp32 tensors that travel BETWEEN layers are temporaries of a call; while a trace buffer is
+ * attached (DEVICE memory, caller-owned, fdg_trace_bytes long, 256-byte aligned; NULL detaches) fdg_forward copies
+ * every layer's fp32 output into it and fdg_backward_delayed every layer's input gradient, with plain device copies
+ * on the call's stream after the kernel that produced them (for measurements: detach).  fdg_trace_read:
+ *   dir 0, layer i             : fp32 output of layer i of the last traced forward (not for heads);
+ *   dir 1, layer i             : gradient of the loss with respect to the INPUT of layer i, as the last traced
+ *                                backward left it (absent for layer 0 of a bottom module);
+ *   dir 1, layer = num_layers  : the gradient that entered the last layer: beta * grad_out (Eq. 15) (not for top modules).
+ * *gated (optional) is set to 1 when a dir-1 tensor was already multiplied by the ReLU gate of the layer below
+ * (its producer did that layer's first backward step, see fdg_kernels.h), else 0.                                */
+fdg_status fdg_saved_read(const fdg_module* m, int64_t seq, int32_t layer, int32_t which, float* host_dst, size_t count,
+                          int32_t shape[4]);
+size_t fdg_trace_bytes(const fdg_module* m);
+fdg_status fdg_trace_attach(fdg_module* m, void* dev_trace, size_t bytes);
+fdg_status fdg_trace_read(const fdg_module* m, int32_t dir, int32_t layer, float* host_dst, size_t count, int32_t shape[4],
+                          int32_t* gated);
+
+/* Per-kernel timing, for measurement only. While enabled, every launch group of a call is bracketed by
  * two HIP events on the call's stream (this costs a few microseconds per launch, so throughput is
  * measured with profiling off).  fdg_profile_enable synchronises the module's stream and clears the
  * records.  fdg_profile_read synchronises, then sums the records into at most `capacity` entries of host

@@ -501,81 +501,87 @@ class OracleModule:
             # gradient shrinking: multiply by beta BEFORE back-propagating (Eq. 15)
             dz = (np.asarray(self.spec.beta, self.dt) * np.ascontiguousarray(grad_out, dtype=self.dt)).astype(self.dt)
         for i in reversed(range(len(self.spec.layers))):
-            L, t = self.spec.layers[i], tapes[i]
-            x = t["x"]
-            need_dx = not (i == 0 and self.spec.is_bottom)
-            if L.kind in (HEAD_POSTACT, HEAD_PREACT):
-                dW, db, dp = k.fc_bwd(t["p"], th[f"{i}.fc.w"], t["dl"])
-                g[f"{i}.fc.w"][...] = dW
-                g[f"{i}.fc.b"][...] = db
-                do = k.avgpool_bwd(dp, t["o_shape"])
-                if L.kind == HEAD_PREACT:
-                    dz = self._bn_back(f"{i}.bn", k.relu_bwd(t["o"], do), th, t, g)
-                else:
-                    dz = do
-            elif L.kind == STEM:
-                dc = q(self._bn_back(f"{i}.bn", k.relu_bwd(t["y"], dz), th, t, g))
-                g[f"{i}.conv.w"][...] = k.conv_bwd_weight(x, dc, 3, L.stride, 1)
-                dz = k.conv_bwd_data(dc, th[f"{i}.conv.w"], x.shape, L.stride, 1) if need_dx else None
-            elif L.kind == BASIC_POSTACT:
-                ds = k.relu_bwd(t["y"], dz)                 # through the final ReLU; feeds both branches
-                dc2 = q(self._bn_back(f"{i}.bn2", ds, th, t, g))
-                g[f"{i}.conv2.w"][...] = k.conv_bwd_weight(t["a1"], dc2, 3, 1, 1)
-                da1 = q(k.conv_bwd_data(dc2, th[f"{i}.conv2.w"], t["a1"].shape, 1, 1))
-                dc1 = q(self._bn_back(f"{i}.bn1", k.relu_bwd(t["a1"], da1), th, t, g))
-                g[f"{i}.conv1.w"][...] = k.conv_bwd_weight(x, dc1, 3, L.stride, 1)
-                if _projects(L):
-                    dpr = q(self._bn_back(f"{i}.bnp", ds, th, t, g))
-                    g[f"{i}.proj.w"][...] = k.conv_bwd_weight(x, dpr, 1, L.stride, 0)
-                if need_dx:
-                    dx = k.conv_bwd_data(dc1, th[f"{i}.conv1.w"], x.shape, L.stride, 1)
-                    if _projects(L):
-                        dx = dx + k.conv_bwd_data(dpr, th[f"{i}.proj.w"], x.shape, L.stride, 0)
-                    else:
-                        dx = dx + ds
-                    dz = dx
-                else:
-                    dz = None
-            elif L.kind == BOTTLENECK_POSTACT:
-                ds = k.relu_bwd(t["y"], dz)                 # through the final ReLU; feeds both branches
-                dc3 = q(self._bn_back(f"{i}.bn3", ds, th, t, g))
-                g[f"{i}.conv3.w"][...] = k.conv_bwd_weight(t["a2"], dc3, 1, 1, 0)
-                da2 = q(k.conv_bwd_data(dc3, th[f"{i}.conv3.w"], t["a2"].shape, 1, 0))
-                dc2 = q(self._bn_back(f"{i}.bn2", k.relu_bwd(t["a2"], da2), th, t, g))
-                g[f"{i}.conv2.w"][...] = k.conv_bwd_weight(t["a1"], dc2, 3, L.stride, 1)
-                da1 = q(k.conv_bwd_data(dc2, th[f"{i}.conv2.w"], t["a1"].shape, L.stride, 1))
-                dc1 = q(self._bn_back(f"{i}.bn1", k.relu_bwd(t["a1"], da1), th, t, g))
-                g[f"{i}.conv1.w"][...] = k.conv_bwd_weight(x, dc1, 1, 1, 0)
-                if _projects(L):
-                    dpr = q(self._bn_back(f"{i}.bnp", ds, th, t, g))
-                    g[f"{i}.proj.w"][...] = k.conv_bwd_weight(x, dpr, 1, L.stride, 0)
-                if need_dx:
-                    dx = k.conv_bwd_data(dc1, th[f"{i}.conv1.w"], x.shape, 1, 0)
-                    if _projects(L):
-                        dx = dx + k.conv_bwd_data(dpr, th[f"{i}.proj.w"], x.shape, L.stride, 0)
-                    else:
-                        dx = dx + ds
-                    dz = dx
-                else:
-                    dz = None
-            elif L.kind == BASIC_PREACT:
-                # y = conv2(o2) + shortcut; the convolutions take the stored copy of the gradient
-                dzb = q(dz)
-                g[f"{i}.conv2.w"][...] = k.conv_bwd_weight(t["o2"], dzb, 3, 1, 1)
-                do2 = q(k.conv_bwd_data(dzb, th[f"{i}.conv2.w"], t["o2"].shape, 1, 1))
-                dc1 = q(self._bn_back(f"{i}.bn2", k.relu_bwd(t["o2"], do2), th, t, g))
-                g[f"{i}.conv1.w"][...] = k.conv_bwd_weight(t["o1"], dc1, 3, L.stride, 1)
-                do1 = k.conv_bwd_data(dc1, th[f"{i}.conv1.w"], t["o1"].shape, L.stride, 1)
-                if _projects(L):
-                    g[f"{i}.proj.w"][...] = k.conv_bwd_weight(t["o1"], dzb, 1, L.stride, 0)
-                    do1 = do1 + k.conv_bwd_data(dzb, th[f"{i}.proj.w"], t["o1"].shape, L.stride, 0)
-                do1 = q(do1)
-                dx = self._bn_back(f"{i}.bn1", k.relu_bwd(t["o1"], do1), th, t, g)   # BN1 needs this even at the bottom
-                if not _projects(L):
-                    dx = dx + dz
-                dz = dx if need_dx else None
+            dz = self._layer_backward(i, self.spec.layers[i], tapes[i], th, dz, g, not (i == 0 and self.spec.is_bottom))
         self.grad = g
         self.has_grad = True
+        return dz
+
+    def _layer_backward(self, i: int, L, t: dict, th: _Flat, dz, g: _Flat, need_dx: bool):
+        """The chain rule (Eq. 8, Eq. 9) through ONE layer: given what the layer's forward kept (t), the parameters
+        of that forward (th) and the gradient dz of its output, writes the layer's parameter gradients into g and
+        returns the gradient of its input (None if not needed)."""
+        k, q = self.k, self._q
+        x = t["x"]
+        if L.kind in (HEAD_POSTACT, HEAD_PREACT):
+            dW, db, dp = k.fc_bwd(t["p"], th[f"{i}.fc.w"], t["dl"])
+            g[f"{i}.fc.w"][...] = dW
+            g[f"{i}.fc.b"][...] = db
+            do = k.avgpool_bwd(dp, t["o_shape"])
+            if L.kind == HEAD_PREACT:
+                dz = self._bn_back(f"{i}.bn", k.relu_bwd(t["o"], do), th, t, g)
+            else:
+                dz = do
+        elif L.kind == STEM:
+            dc = q(self._bn_back(f"{i}.bn", k.relu_bwd(t["y"], dz), th, t, g))
+            g[f"{i}.conv.w"][...] = k.conv_bwd_weight(x, dc, 3, L.stride, 1)
+            dz = k.conv_bwd_data(dc, th[f"{i}.conv.w"], x.shape, L.stride, 1) if need_dx else None
+        elif L.kind == BASIC_POSTACT:
+            ds = k.relu_bwd(t["y"], dz)                 # through the final ReLU; feeds both branches
+            dc2 = q(self._bn_back(f"{i}.bn2", ds, th, t, g))
+            g[f"{i}.conv2.w"][...] = k.conv_bwd_weight(t["a1"], dc2, 3, 1, 1)
+            da1 = q(k.conv_bwd_data(dc2, th[f"{i}.conv2.w"], t["a1"].shape, 1, 1))
+            dc1 = q(self._bn_back(f"{i}.bn1", k.relu_bwd(t["a1"], da1), th, t, g))
+            g[f"{i}.conv1.w"][...] = k.conv_bwd_weight(x, dc1, 3, L.stride, 1)
+            if _projects(L):
+                dpr = q(self._bn_back(f"{i}.bnp", ds, th, t, g))
+                g[f"{i}.proj.w"][...] = k.conv_bwd_weight(x, dpr, 1, L.stride, 0)
+            if need_dx:
+                dx = k.conv_bwd_data(dc1, th[f"{i}.conv1.w"], x.shape, L.stride, 1)
+                if _projects(L):
+                    dx = dx + k.conv_bwd_data(dpr, th[f"{i}.proj.w"], x.shape, L.stride, 0)
+                else:
+                    dx = dx + ds
+                dz = dx
+            else:
+                dz = None
+        elif L.kind == BOTTLENECK_POSTACT:
+            ds = k.relu_bwd(t["y"], dz)                 # through the final ReLU; feeds both branches
+            dc3 = q(self._bn_back(f"{i}.bn3", ds, th, t, g))
+            g[f"{i}.conv3.w"][...] = k.conv_bwd_weight(t["a2"], dc3, 1, 1, 0)
+            da2 = q(k.conv_bwd_data(dc3, th[f"{i}.conv3.w"], t["a2"].shape, 1, 0))
+            dc2 = q(self._bn_back(f"{i}.bn2", k.relu_bwd(t["a2"], da2), th, t, g))
+            g[f"{i}.conv2.w"][...] = k.conv_bwd_weight(t["a1"], dc2, 3, L.stride, 1)
+            da1 = q(k.conv_bwd_data(dc2, th[f"{i}.conv2.w"], t["a1"].shape, L.stride, 1))
+            dc1 = q(self._bn_back(f"{i}.bn1", k.relu_bwd(t["a1"], da1), th, t, g))
+            g[f"{i}.conv1.w"][...] = k.conv_bwd_weight(x, dc1, 1, 1, 0)
+            if _projects(L):
+                dpr = q(self._bn_back(f"{i}.bnp", ds, th, t, g))
+                g[f"{i}.proj.w"][...] = k.conv_bwd_weight(x, dpr, 1, L.stride, 0)
+            if need_dx:
+                dx = k.conv_bwd_data(dc1, th[f"{i}.conv1.w"], x.shape, 1, 0)
+                if _projects(L):
+                    dx = dx + k.conv_bwd_data(dpr, th[f"{i}.proj.w"], x.shape, L.stride, 0)
+                else:
+                    dx = dx + ds
+                dz = dx
+            else:
+                dz = None
+        elif L.kind == BASIC_PREACT:
+            # y = conv2(o2) + shortcut; the convolutions take the stored copy of the gradient
+            dzb = q(dz)
+            g[f"{i}.conv2.w"][...] = k.conv_bwd_weight(t["o2"], dzb, 3, 1, 1)
+            do2 = q(k.conv_bwd_data(dzb, th[f"{i}.conv2.w"], t["o2"].shape, 1, 1))
+            dc1 = q(self._bn_back(f"{i}.bn2", k.relu_bwd(t["o2"], do2), th, t, g))
+            g[f"{i}.conv1.w"][...] = k.conv_bwd_weight(t["o1"], dc1, 3, L.stride, 1)
+            do1 = k.conv_bwd_data(dc1, th[f"{i}.conv1.w"], t["o1"].shape, L.stride, 1)
+            if _projects(L):
+                g[f"{i}.proj.w"][...] = k.conv_bwd_weight(t["o1"], dzb, 1, L.stride, 0)
+                do1 = do1 + k.conv_bwd_data(dzb, th[f"{i}.proj.w"], t["o1"].shape, L.stride, 0)
+            do1 = q(do1)
+            dx = self._bn_back(f"{i}.bn1", k.relu_bwd(t["o1"], do1), th, t, g)   # BN1 needs this even at the bottom
+            if not _projects(L):
+                dx = dx + dz
+            dz = dx if need_dx else None
         return dz
 
     # ---- update --------------------------------------------------------------------------------

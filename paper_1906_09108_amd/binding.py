@@ -47,6 +47,7 @@ EXPORTS = ["fdg_module_workspace_bytes", "fdg_module_create", "fdg_module_worksp
            "fdg_destroy", "fdg_param_count", "fdg_set_params", "fdg_get_params", "fdg_get_grads", "fdg_get_momentum",
            "fdg_bn_stat_count", "fdg_get_bn_running", "fdg_output_shape", "fdg_queue_state", "fdg_status_string",
            "fdg_profile_enable", "fdg_profile_read", "fdg_input_shape", "fdg_module_traits",
+           "fdg_saved_read", "fdg_trace_bytes", "fdg_trace_attach", "fdg_trace_read",
            "fdg_chain_mailbox_bytes", "fdg_chain_create", "fdg_chain_step", "fdg_chain_state", "fdg_chain_destroy"]
 
 
@@ -84,6 +85,12 @@ def load() -> ctypes.CDLL:
     lib.fdg_input_shape.argtypes, lib.fdg_input_shape.restype = [vp, ctypes.POINTER(i32 * 4)], i32
     lib.fdg_module_traits.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.fdg_module_traits.restype = i32
+    lib.fdg_saved_read.argtypes = [vp, ctypes.c_int64, i32, i32, vp, sz, ctypes.POINTER(i32 * 4)]
+    lib.fdg_saved_read.restype = i32
+    lib.fdg_trace_bytes.argtypes, lib.fdg_trace_bytes.restype = [vp], sz
+    lib.fdg_trace_attach.argtypes, lib.fdg_trace_attach.restype = [vp, vp, sz], i32
+    lib.fdg_trace_read.argtypes = [vp, i32, i32, vp, sz, ctypes.POINTER(i32 * 4), ctypes.POINTER(i32)]
+    lib.fdg_trace_read.restype = i32
     lib.fdg_chain_mailbox_bytes.argtypes, lib.fdg_chain_mailbox_bytes.restype = [ctypes.POINTER(vp), i32], sz
     lib.fdg_chain_create.argtypes, lib.fdg_chain_create.restype = [ctypes.POINTER(vp), i32, vp, sz, ctypes.POINTER(vp)], i32
     lib.fdg_chain_step.argtypes, lib.fdg_chain_step.restype = [vp, vp, vp, f32, vp, ctypes.POINTER(i32), vp], i32
@@ -316,6 +323,52 @@ class FdgModule:
         return [dict(name=arr[i].name.decode(), kernel=arr[i].kernel.decode(), calls=int(arr[i].calls),
                      total_ms=float(arr[i].total_ms), flops=float(arr[i].flops), bytes=float(arr[i].bytes))
                 for i in range(min(n.value, cap))]
+
+    # -- parity accessors (include/fdg.h): one C call each; the first call with a one-element buffer only asks for the shape
+    def saved_read(self, seq: int, layer: int, which: int) -> np.ndarray:
+        """A tensor of the saved forward `seq` as host float32 NCHW."""
+        shp = (ctypes.c_int32 * 4)()
+        probe = np.empty(1, np.float32)
+        load().fdg_saved_read(self.handle, int(seq), int(layer), int(which), probe.ctypes.data, 0, ctypes.byref(shp))
+        shape = tuple(int(v) for v in shp)
+        if min(shape) <= 0:
+            raise FdgError(FDG_ERR_INVALID_ARG, f"fdg_saved_read(seq={seq}, layer={layer}, which={which})")
+        out = np.empty(shape, np.float32)
+        st = load().fdg_saved_read(self.handle, int(seq), int(layer), int(which), out.ctypes.data, out.size, ctypes.byref(shp))
+        if st != FDG_OK:
+            raise FdgError(st, f"fdg_saved_read(seq={seq}, layer={layer}, which={which})")
+        return out
+
+    def trace_attach(self) -> None:
+        """Allocates a trace buffer (torch owns the memory) and attaches it."""
+        t = self.torch
+        nbytes = int(load().fdg_trace_bytes(self.handle))
+        self._trace = t.empty(nbytes + 256, dtype=t.uint8, device=self.device)
+        off = (-self._trace.data_ptr()) % 256
+        st = load().fdg_trace_attach(self.handle, int(self._trace.data_ptr()) + off, nbytes)
+        if st != FDG_OK:
+            raise FdgError(st, "fdg_trace_attach")
+
+    def trace_detach(self) -> None:
+        st = load().fdg_trace_attach(self.handle, None, 0)
+        if st != FDG_OK:
+            raise FdgError(st, "fdg_trace_attach")
+        self._trace = None
+
+    def trace_read(self, direction: int, layer: int) -> Tuple[np.ndarray, bool]:
+        """(tensor as host float32 NCHW, already gated by the layer below)."""
+        shp, gated = (ctypes.c_int32 * 4)(), ctypes.c_int32()
+        probe = np.empty(1, np.float32)
+        load().fdg_trace_read(self.handle, int(direction), int(layer), probe.ctypes.data, 0, ctypes.byref(shp), ctypes.byref(gated))
+        shape = tuple(int(v) for v in shp)
+        if min(shape) <= 0:
+            raise FdgError(FDG_ERR_INVALID_ARG, f"fdg_trace_read(dir={direction}, layer={layer})")
+        out = np.empty(shape, np.float32)
+        st = load().fdg_trace_read(self.handle, int(direction), int(layer), out.ctypes.data, out.size, ctypes.byref(shp),
+                                   ctypes.byref(gated))
+        if st != FDG_OK:
+            raise FdgError(st, f"fdg_trace_read(dir={direction}, layer={layer})")
+        return out, bool(gated.value)
 
     def queue_state(self) -> Tuple[int, int, int]:
         o, a, b = ctypes.c_int32(), ctypes.c_int64(), ctypes.c_int64()

@@ -77,6 +77,10 @@ struct Plan {
   size_t o_S[2] = {0, 0}, o_G[2] = {0, 0}, o_GB[2] = {0, 0}, o_T[2] = {0, 0}, o_TP = 0, o_TPB = 0, o_dp = 0;
   size_t o_wscratch = 0, wscratch_bytes = 0;   // partial sums of the split weight gradient
   size_t total = 0;
+  // layout of a caller-provided trace buffer (parity accessors): per layer the fp32 output of the forward and the fp32
+  // input gradient of the backward, [L.size()] = the gradient that entered the module, all NHWC as the kernels leave them
+  std::vector<size_t> tr_fwd, tr_bwd;
+  size_t trace_total = 0;
 };
 
 bool build_plan(const fdg_module_desc* desc, int save_mode, Plan& p, fdg_status* why) {
@@ -320,6 +324,17 @@ bool build_plan(const fdg_module_desc* desc, int save_mode, Plan& p, fdg_status*
   for (const ConvInfo& ci : p.convs) p.wscratch_bytes = std::max(p.wscratch_bytes, conv_wgrad_scratch_bytes(ci.sh));
   p.o_wscratch = take(p.wscratch_bytes);
   p.total = o;
+  {
+    size_t to = 0;
+    auto ttake = [&](size_t bytes) { const size_t at = to; to += align_up(bytes, kAlign); return at; };
+    for (const LayerPlan& L : p.L) {
+      const bool head = L.kind == FDG_HEAD_POSTACT || L.kind == FDG_HEAD_PREACT;
+      p.tr_fwd.push_back(ttake(head ? 0 : (size_t)N * L.Ho * L.Wo * L.c_out * 4));
+      p.tr_bwd.push_back(ttake((size_t)N * L.Hi * L.Wi * round8(L.c_in) * 4));
+    }
+    p.tr_bwd.push_back(ttake(p.is_top ? 0 : (size_t)N * p.out_h * p.out_w * p.out_c * 4));
+    p.trace_total = to;
+  }
   *why = FDG_OK;
   return true;
 }
@@ -382,6 +397,9 @@ struct fdg_module {
   bool has_grad = false;
   hipStream_t last_stream = nullptr;
   hipStream_t fwd_stream = nullptr;   // the forward's last stream (it may differ from the backward's)
+  char* trace = nullptr;              // attached trace buffer (parity accessors), or nullptr
+  std::vector<char> tr_gated;         // per layer: the traced input gradient is already gated by the layer below
+  bool tr_fwd_valid = false, tr_bwd_valid = false;
 
   float* params() const { return reinterpret_cast<float*>(ws + p.o_params); }
   float* mom() const { return reinterpret_cast<float*>(ws + p.o_mom); }
@@ -761,10 +779,13 @@ fdg_status forward_pass(fdg_module* m, const SlotView& v, const float* x_dev, fl
       FDG_TRY(launch_softmax_ce(v.logits(), v.labels(), y_dev, v.dl(), N, J, s));
       break;
     }
+    if (m->trace && !replayed)
+      FDG_TRY(hipMemcpyAsync(m->trace + p.tr_fwd[li], m->S(nxt), (size_t)N * L.Ho * L.Wo * L.c_out * 4, hipMemcpyDeviceToDevice, s));
     cur = nxt;
     cur_b = v.act(L.out_b);
     stats_ready = next_ready;
   }
+  if (m->trace && !replayed) m->tr_fwd_valid = true;
   if (!p.is_top && y_dev) FDG_TRY(launch_nhwc_to_nchw(m->S(cur), y_dev, N, p.out_c, p.out_h * p.out_w, p.out_c, s));
   return FDG_OK;
 }
@@ -805,6 +826,7 @@ fdg_status fdg_module_create_ex(const fdg_module_desc* desc, int32_t save_mode, 
     return dev_workspace ? FDG_ERR_WORKSPACE_TOO_SMALL : FDG_ERR_INVALID_ARG;
   }
   m->ws = static_cast<char*>(dev_workspace);
+  m->tr_gated.assign(m->p.L.size(), 0);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   m->last_stream = s;
   m->fwd_stream = s;
@@ -883,6 +905,9 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
   int cur = 0;
   if (!p.is_top)  // gradient shrinking of Eq. 15: multiply by beta before anything else
     FDG_TRY(launch_nchw_to_nhwc(grad_out_dev, m->G(cur), m->GB(cur), N, p.out_c, p.out_h * p.out_w, p.out_c, p.d.beta, s));
+  if (m->trace && !p.is_top)
+    FDG_TRY(hipMemcpyAsync(m->trace + p.tr_bwd[p.L.size()], m->G(cur), (size_t)N * p.out_h * p.out_w * p.out_c * 4,
+                           hipMemcpyDeviceToDevice, s));
   static const bool no_feed = getenv("FDG_NO_GATED_DGRAD") != nullptr || getenv("FDG_NO_FEED") != nullptr;   // A/B switches for measurements
   bool fed = false;   // G(cur) came from the layer above already gated by this layer's output, with this layer's
                       // last batch norm's two sums in bsums
@@ -1009,8 +1034,14 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
                                        need_dx ? m->G(nxt) : nullptr, need_dx ? m->GB(nxt) : nullptr, s));
       }
     }
+    if (m->trace && need_dx) {
+      FDG_TRY(hipMemcpyAsync(m->trace + p.tr_bwd[li], m->G(nxt), (size_t)N * L.Hi * L.Wi * round8(L.c_in) * 4,
+                             hipMemcpyDeviceToDevice, s));
+      m->tr_gated[li] = fed ? 1 : 0;
+    }
     cur = nxt;
   }
+  if (m->trace) m->tr_bwd_valid = true;
   if (grad_in_dev && !p.d.is_bottom)
     FDG_TRY(launch_nhwc_to_nchw(m->G(cur), grad_in_dev, N, p.d.c_in, p.d.h_in * p.d.w_in, p.Cp_in, s));
   FDG_TRY(side_join(m, s));   // the gradient is complete when the call's stream gets here
@@ -1143,6 +1174,133 @@ fdg_status fdg_queue_state(const fdg_module* m, int32_t* outstanding, int64_t* o
   if (oldest_seq) *oldest_seq = n ? m->seq_bwd : -1;
   if (newest_seq) *newest_seq = n ? m->seq_fwd - 1 : -1;
   return FDG_OK;
+}
+
+// ---- parity accessors ----
+static fdg_status sync_streams(const fdg_module* m) {
+  FDG_TRY(hipStreamSynchronize(m->last_stream));
+  if (m->fwd_stream != m->last_stream) FDG_TRY(hipStreamSynchronize(m->fwd_stream));
+  return FDG_OK;
+}
+// device [n, hw, cp] (bf16 or fp32) -> host fp32 [n, c, hw]
+static fdg_status read_nhwc(const void* dev, bool is_b16, int n, int c, int cp, int hw, float* host_dst) {
+  const size_t elems = (size_t)n * hw * cp;
+  std::vector<float> f(elems);
+  if (is_b16) {
+    std::vector<uint16_t> raw(elems);
+    FDG_TRY(hipMemcpy(raw.data(), dev, elems * 2, hipMemcpyDeviceToHost));
+    for (size_t i = 0; i < elems; ++i) {
+      const uint32_t u = (uint32_t)raw[i] << 16;
+      memcpy(&f[i], &u, 4);
+    }
+  } else {
+    FDG_TRY(hipMemcpy(f.data(), dev, elems * 4, hipMemcpyDeviceToHost));
+  }
+  for (int i = 0; i < n; ++i)
+    for (int q = 0; q < hw; ++q)
+      for (int k = 0; k < c; ++k) host_dst[((size_t)i * c + k) * hw + q] = f[((size_t)i * hw + q) * cp + k];
+  return FDG_OK;
+}
+
+fdg_status fdg_saved_read(const fdg_module* m, int64_t seq, int32_t layer, int32_t which, float* host_dst, size_t count,
+                          int32_t shape[4]) {
+  if (!m || !host_dst || layer < 0 || layer >= (int)m->p.L.size()) return FDG_ERR_INVALID_ARG;
+  const Plan& p = m->p;
+  if (seq < 0 || seq >= m->seq_fwd || seq < m->seq_fwd - (p.d.delay + 1)) return FDG_ERR_INVALID_ARG;
+  if (p.replay && seq != m->seq_bwd - 1) return FDG_ERR_INVALID_ARG;   // one set of intermediates: the last replayed context's
+  const LayerPlan& L = p.L[layer];
+  const SlotView v = view_of(m, seq);
+  const int N = p.d.n;
+  const bool head = L.kind == FDG_HEAD_POSTACT || L.kind == FDG_HEAD_PREACT;
+  const void* dev = nullptr;
+  bool b16 = true;
+  int c = 0, h = 0, w = 0;
+  const int cm = L.c_out / 4;
+  if (which >= 0 && which <= 5) {
+    // which intermediates a layer kind has, with their shapes
+    bool has = false;
+    c = L.c_out; h = L.Ho; w = L.Wo;
+    switch (L.kind) {
+      case FDG_STEM_CONV_BN_RELU: has = which == 0; break;
+      case FDG_BASIC_POSTACT: has = which <= 2 || (which == 3 && L.projects); break;
+      case FDG_BASIC_PREACT:
+        has = which <= 2;
+        if (which == 0) { c = L.c_in; h = L.Hi; w = L.Wi; }
+        break;
+      case FDG_BOTTLENECK_POSTACT:
+        has = which != 3 || L.projects;
+        if (which == 0 || which == 1) { c = cm; h = L.Hi; w = L.Wi; }
+        if (which == 2 || which == 4) c = cm;
+        break;
+      case FDG_HEAD_PREACT: has = which == 0; c = L.c_in; h = L.Hi; w = L.Wi; break;
+      default: break;
+    }
+    if (!has) return FDG_ERR_INVALID_ARG;
+    dev = v.act(L.act[which]);
+  } else if (which == 6) {
+    if (head) return FDG_ERR_INVALID_ARG;
+    c = L.c_out; h = L.Ho; w = L.Wo;
+    dev = v.act(L.out_b);
+  } else if (which == 7) {
+    c = L.c_in; h = L.Hi; w = L.Wi;
+    dev = layer == 0 ? v.xin() : v.act(p.L[layer - 1].out_b);
+  } else if (which == 8 || which == 9) {
+    if (!head) return FDG_ERR_INVALID_ARG;
+    b16 = false;
+    c = which == 8 ? p.head_C : p.d.num_classes; h = w = 1;
+    dev = which == 8 ? v.pooled() : v.dl();
+  } else {
+    return FDG_ERR_INVALID_ARG;
+  }
+  if (shape) { shape[0] = N; shape[1] = c; shape[2] = h; shape[3] = w; }
+  if (count != (size_t)N * c * h * w) return FDG_ERR_INVALID_ARG;
+  if (fdg_status st = sync_streams(m); st != FDG_OK) return st;
+  return read_nhwc(dev, b16, N, c, b16 ? round8(c) : c, h * w, host_dst);   // the head's fp32 tensors are dense
+}
+
+size_t fdg_trace_bytes(const fdg_module* m) { return m ? m->p.trace_total : 0; }
+
+fdg_status fdg_trace_attach(fdg_module* m, void* dev_trace, size_t bytes) {
+  if (!m) return FDG_ERR_INVALID_ARG;
+  if (dev_trace && (bytes < m->p.trace_total || (reinterpret_cast<uintptr_t>(dev_trace) % kAlign) != 0))
+    return FDG_ERR_WORKSPACE_TOO_SMALL;
+  if (fdg_status st = sync_streams(m); st != FDG_OK) return st;
+  m->trace = static_cast<char*>(dev_trace);
+  m->tr_fwd_valid = m->tr_bwd_valid = false;
+  return FDG_OK;
+}
+
+fdg_status fdg_trace_read(const fdg_module* m, int32_t dir, int32_t layer, float* host_dst, size_t count, int32_t shape[4],
+                          int32_t* gated) {
+  if (!m || !host_dst || !m->trace || (dir != 0 && dir != 1)) return FDG_ERR_INVALID_ARG;
+  const Plan& p = m->p;
+  const int nl = (int)p.L.size(), N = p.d.n;
+  int c = 0, h = 0, w = 0;
+  size_t off = 0;
+  int g = 0;
+  if (dir == 0) {
+    if (layer < 0 || layer >= nl || !m->tr_fwd_valid) return FDG_ERR_INVALID_ARG;
+    const LayerPlan& L = p.L[layer];
+    if (L.kind == FDG_HEAD_POSTACT || L.kind == FDG_HEAD_PREACT) return FDG_ERR_INVALID_ARG;
+    c = L.c_out; h = L.Ho; w = L.Wo; off = p.tr_fwd[layer];
+  } else {
+    if (layer < 0 || layer > nl || !m->tr_bwd_valid) return FDG_ERR_INVALID_ARG;
+    if (layer == nl) {
+      if (p.is_top) return FDG_ERR_INVALID_ARG;
+      c = p.out_c; h = p.out_h; w = p.out_w;
+    } else {
+      if (layer == 0 && p.d.is_bottom) return FDG_ERR_INVALID_ARG;
+      const LayerPlan& L = p.L[layer];
+      c = L.c_in; h = L.Hi; w = L.Wi;
+      g = m->tr_gated[layer];
+    }
+    off = p.tr_bwd[layer];
+  }
+  if (shape) { shape[0] = N; shape[1] = c; shape[2] = h; shape[3] = w; }
+  if (gated) *gated = g;
+  if (count != (size_t)N * c * h * w) return FDG_ERR_INVALID_ARG;
+  if (fdg_status st = sync_streams(m); st != FDG_OK) return st;
+  return read_nhwc(m->trace + off, false, N, c, round8(c), h * w, host_dst);
 }
 
 fdg_status fdg_profile_enable(fdg_module* m, int enable) {

@@ -1,8 +1,13 @@
-"""Drives the HIP module (through the C ABI) and the CPU oracle side by side on the same seeded inputs.
+"""Drives the HIP module (through the C ABI) and the CPU oracle side by side on the same seeded inputs, END TO END.
+(The sharp comparison -- every layer of a real step against its definition on the input that layer saw, to 1e-3 --
+is tests/layerwise.py / tests/test_gpu_layerwise.py; this harness checks the whole chain: sequencing over iterations,
+the ring, the update, and that nothing beyond rounding noise separates the two paths.)
 
-Three runs advance in lock step through the same iterations:
+Four runs advance in lock step through the same iterations:
   gpu    the HIP path;
   same   the oracle in its bf16-storage mode (decisions taken in the kernel's precision);
+  noisy  the same oracle run again with every convolution result (forward, data and weight gradient) perturbed by
+         3e-7 of its rms BEFORE it is stored -- what a different order of the fp32 sums does, and nothing else;
   plain  the oracle's fp32 definition.
 
 What can be asked of a bf16 path.  The module is a deep composition of ReLU gates.  Rounding an
@@ -20,14 +25,14 @@ Hence two bars:
       both shortcut forms are covered by such modules).  The input gradient carries single gated
       elements unreduced; a few gates sit within a rounding of zero and are valid either way, so it is
       held to the bar on all but TIE_FRACTION of its elements and in relative L2 norm.
-  ENVELOPE (every module, every iteration): relL2(gpu, same) <= 2e-2 + 2 * relL2(same, plain): the HIP
-      path may not be further from the kernel-precision oracle than bf16 storage itself is from the
-      definition.  A wiring or indexing mistake gives errors of order one and breaks either bar
-      wherever `inherent` is below one half.  Where it is above (gradients of the 27- and 150-block
-      modules: there the definition and its own bf16-storage evaluation are already unrelated vectors)
-      the comparison carries no information and is only reported; for those modules the proof is
-      carried by the per-kernel tests at their real shapes (tests/test_gpu_kernels.py), by their
-      forwards, and by the shallow modules built from the same blocks.
+  ENVELOPE (every module, every iteration): relL2(gpu, same) <= 2e-2 + 2 * floor, floor = relL2(noisy, same):
+      the HIP path may not be further from the kernel-precision oracle than that oracle is from ITSELF when only
+      the order of its sums changes (tests/test_oracle_module.py pins on the CPU that this floor is what the
+      module's depth makes of 3e-7, and that it has the size of the distance to the fp32 definition where the
+      latter is large).  A wiring or indexing mistake gives errors of order one and breaks the bar wherever the
+      floor is below one half.  Where it is above, the end-to-end comparison of that tensor carries no
+      information: the record counts as NOT COVERED here (the count is printed per module) and its proof is
+      the layer-by-layer test, which covers every layer of every benchmark module at 1e-3.
 Queue indices and sequence numbers are compared exactly, always."""
 from __future__ import annotations
 
@@ -78,20 +83,41 @@ def rel_l2(got, ref) -> float:
     return float(np.linalg.norm(got - ref) / d) if d > 0 else (0.0 if np.linalg.norm(got) == 0 else float("inf"))
 
 
+SUMMATION_NOISE = 3e-7   # of a convolution result's rms: the size of a changed order of its fp32 sums
+
+
+def with_summation_noise(om, seed: int, eps: float = SUMMATION_NOISE):
+    """Makes the three convolution routines of ONE oracle module (its own Kernels object) add N(0, (eps*rms)^2) to
+    their results before anything is rounded or stored.  Returns om."""
+    r = np.random.default_rng(seed)
+
+    def wrap(fn):
+        def noisy(*a, **kw):
+            y = fn(*a, **kw)
+            scale = float(np.sqrt((y.astype(np.float64) ** 2).mean()))
+            return (y + (eps * scale) * r.standard_normal(y.shape)).astype(y.dtype)
+        return noisy
+    om.k.conv_fwd, om.k.conv_bwd_data, om.k.conv_bwd_weight = wrap(om.k.conv_fwd), wrap(om.k.conv_bwd_data), wrap(om.k.conv_bwd_weight)
+    return om
+
+
 class Record:
     """One tensor at one iteration: strict measure (max norm, or the tie-robust one for grad_in), relative
-    L2 against the kernel-precision oracle, and the inherent distance of that oracle from the definition."""
+    L2 against the kernel-precision oracle, the floor (distance of that oracle from its own run with summation
+    noise) and the inherent distance of that oracle from the fp32 definition (reported only)."""
 
-    def __init__(self, label: str, step: int, strict: float, l2: float, inherent: float):
+    def __init__(self, label: str, step: int, strict: float, l2: float, inherent: float, floor: float = 0.0,
+                 l2_plain: float = 0.0):
         self.label, self.step, self.strict, self.l2, self.inherent = label, step, strict, l2, inherent
+        self.floor, self.l2_plain = floor, l2_plain
 
     @property
     def informative(self) -> bool:
-        return self.inherent <= INFORMATIVE_LIMIT
+        return self.floor <= INFORMATIVE_LIMIT
 
     @property
     def envelope_ok(self) -> bool:
-        return (not self.informative) or self.l2 <= TOL + ENVELOPE_FACTOR * self.inherent
+        return (not self.informative) or self.l2 <= TOL + ENVELOPE_FACTOR * self.floor
 
     @property
     def strict_ok(self) -> bool:
@@ -118,9 +144,10 @@ def run_side_by_side(spec, steps: int, seed: int = 0, perturb_bn: bool = True, b
 
     theta0 = W.make_params(spec, seed, perturb_bn=perturb_bn)
     same = OracleModule(spec, np.float32, storage="bf16")
+    noisy = with_summation_noise(OracleModule(spec, np.float32, storage="bf16"), seed + 1000)
     plain = OracleModule(spec, np.float32, storage="fp32")
     gpu = FdgModule(spec, device, save_mode=save_mode)
-    for m in (same, plain, gpu):
+    for m in (same, noisy, plain, gpu):
         m.set_params(theta0)
     records: List[Record] = []
     exact: List[str] = []
@@ -129,9 +156,10 @@ def run_side_by_side(spec, steps: int, seed: int = 0, perturb_bn: bool = True, b
     total = d + steps
     grad_in = None if spec.is_bottom else torch.empty(spec.input_shape(), dtype=torch.float32, device=dev)
 
-    def note(label, step, got, ref_same, ref_plain, robust=False):
+    def note(label, step, got, ref_same, ref_plain, ref_noisy, robust=False):
         strict = rel_err_robust(got, ref_same) if robust else rel_err(got, ref_same)
-        records.append(Record(label, step, strict, rel_l2(got, ref_same), rel_l2(ref_same, ref_plain)))
+        records.append(Record(label, step, strict, rel_l2(got, ref_same), rel_l2(ref_same, ref_plain),
+                              rel_l2(ref_noisy, ref_same), rel_l2(got, ref_plain)))
 
     def check_queue(tag):
         if gpu.queue_state() != same.queue_state():
@@ -140,35 +168,35 @@ def run_side_by_side(spec, steps: int, seed: int = 0, perturb_bn: bool = True, b
     def do_forward(t):
         x = W.make_input(spec, t, seed)
         labels = W.make_labels(spec, t, seed)
-        y_same, y_plain = same.forward(x, labels), plain.forward(x, labels)
+        y_same, y_plain, y_noisy = same.forward(x, labels), plain.forward(x, labels), noisy.forward(x, labels)
         y = gpu.forward(torch.from_numpy(x).to(dev), None if labels is None else torch.from_numpy(labels).to(dev))
         y = y.cpu().numpy()
         if spec.is_top:
-            note("loss", t, y[:1], y_same[:1], y_plain[:1])
-            note("logits", t, y[1:], y_same[1:], y_plain[1:])
+            note("loss", t, y[:1], y_same[:1], y_plain[:1], y_noisy[:1])
+            note("logits", t, y[1:], y_same[1:], y_plain[1:], y_noisy[1:])
         else:
-            note("y", t, y, y_same, y_plain)
+            note("y", t, y, y_same, y_plain, y_noisy)
         check_queue(f"after forward {t}")
 
     def do_backward_update(t):
         s = t - d                                  # the batch whose gradient arrives at iteration t
         g = W.make_grad_out(spec, s, seed)
-        gin_same, gin_plain = same.backward_delayed(g), plain.backward_delayed(g)
+        gin_same, gin_plain, gin_noisy = same.backward_delayed(g), plain.backward_delayed(g), noisy.backward_delayed(g)
         gpu.backward_delayed(None if g is None else torch.from_numpy(g).to(dev), grad_in)
         check_queue(f"after backward {t}")
-        for (name, a), (_, b), (_, c) in zip(_split(spec, gpu.get_grads()), _split(spec, same.get_grads()),
-                                             _split(spec, plain.get_grads())):
-            note("grad:" + name, t, a, b, c)
+
+        def four(get):
+            return zip(_split(spec, get(gpu)), _split(spec, get(same)), _split(spec, get(plain)), _split(spec, get(noisy)))
+        for (name, a), (_, b), (_, c), (_, e) in four(lambda m: m.get_grads()):
+            note("grad:" + name, t, a, b, c, e)
         if gin_same is not None:
-            note("grad_in", t, grad_in.cpu().numpy(), gin_same, gin_plain, robust=True)
-        for m in (same, plain, gpu):
+            note("grad_in", t, grad_in.cpu().numpy(), gin_same, gin_plain, gin_noisy, robust=True)
+        for m in (same, noisy, plain, gpu):
             m.update(spec.lr)
-        for (name, a), (_, b), (_, c) in zip(_split(spec, gpu.get_params()), _split(spec, same.get_params()),
-                                             _split(spec, plain.get_params())):
-            note("theta:" + name, t, a, b, c)
-        for (name, a), (_, b), (_, c) in zip(_split(spec, gpu.get_momentum()), _split(spec, same.get_momentum()),
-                                             _split(spec, plain.get_momentum())):
-            note("v:" + name, t, a, b, c)
+        for (name, a), (_, b), (_, c), (_, e) in four(lambda m: m.get_params()):
+            note("theta:" + name, t, a, b, c, e)
+        for (name, a), (_, b), (_, c), (_, e) in four(lambda m: m.get_momentum()):
+            note("v:" + name, t, a, b, c, e)
 
     if backward_first:
         # order of Algorithm I: delayed backward -> update -> forward.  Needs d >= 1 (a delay-0 module
@@ -185,29 +213,44 @@ def run_side_by_side(spec, steps: int, seed: int = 0, perturb_bn: bool = True, b
             if t >= d:
                 do_backward_update(t)
     if gpu.get_bn_running().size:
-        note("bn_running", total - 1, gpu.get_bn_running(), same.get_bn_running(), plain.get_bn_running())
+        note("bn_running", total - 1, gpu.get_bn_running(), same.get_bn_running(), plain.get_bn_running(),
+             noisy.get_bn_running())
     gpu.close()
     return records, exact
 
 
-def judge(records: List[Record], spec, strict: bool) -> List[str]:
+def judge(records: List[Record], spec, strict: bool, deep: bool = False) -> List[str]:
     """Failure messages.  ENVELOPE applies to every record; STRICT to the forwards up to, and the gradients
-    of, the first backward (the first update re-rounds the weights of the runs independently)."""
+    of, the first backward (the first update re-rounds the weights of the runs independently).
+    A module none of whose gradient tensors is covered end to end fails unless the caller says it is `deep`
+    (the 27- and 150-block modules, whose gradients are covered layer by layer in tests/test_gpu_layerwise.py)."""
     bad = []
     t0 = spec.delay
+    n, silent, asserted_bwd = coverage(records)
+    if asserted_bwd == 0 and not deep and any(r.label.startswith("grad:") for r in records):
+        bad.append(f"no gradient tensor of this module is covered end to end ({silent} of {n} records beyond the floor limit)")
     for r in records:
         if not r.envelope_ok:
-            bad.append(f"ENVELOPE step {r.step} {r.label}: L2 {r.l2:.3e} > {TOL} + {ENVELOPE_FACTOR} * inherent {r.inherent:.3e}")
+            bad.append(f"ENVELOPE step {r.step} {r.label}: L2 {r.l2:.3e} > {TOL} + {ENVELOPE_FACTOR} * floor {r.floor:.3e}")
         if strict and r.step <= t0 and not r.label.startswith(("theta:", "v:", "bn_running")) and not r.strict_ok:
             bad.append(f"STRICT step {r.step} {r.label}: {r.strict:.3e} (L2 {r.l2:.3e}) over {TOL}")
     return bad
 
 
+def coverage(records: List[Record]) -> Tuple[int, int, int]:
+    """(records, records NOT COVERED because their floor is beyond the informative range, backward tensors asserted)."""
+    silent = sum(1 for r in records if not r.informative)
+    asserted_bwd = sum(1 for r in records if r.informative and r.label.startswith(("grad:", "grad_in")))
+    return len(records), silent, asserted_bwd
+
+
 def format_report(records: List[Record], limit: int = 30) -> str:
     rows = sorted(records, key=lambda r: -r.strict)[:limit]
-    silent = sum(1 for r in records if not r.informative)
-    lines = [f"  {len(records)} tensor records, {silent} beyond the informative range (inherent > {INFORMATIVE_LIMIT})",
-             f"  {'tensor':34s} step   strict      L2    inherent(L2)"]
+    n, silent, asserted_bwd = coverage(records)
+    lines = [f"  {n} tensor records, {silent} NOT COVERED end to end (floor > {INFORMATIVE_LIMIT}), "
+             f"{asserted_bwd} gradient tensors asserted",
+             f"  {'tensor':34s} step  strict   L2(gpu,same)  floor=L2(noisy,same)  L2(same,plain)  L2(gpu,plain)"]
     for r in rows:
-        lines.append(f"  {r.label:34s} {r.step:3d}  {r.strict:.2e}  {r.l2:.2e}  {r.inherent:.2e}")
+        lines.append(f"  {r.label:34s} {r.step:3d}  {r.strict:.2e}  {r.l2:.2e}      {r.floor:.2e}              {r.inherent:.2e}"
+                     f"        {r.l2_plain:.2e}")
     return "\n".join(lines)

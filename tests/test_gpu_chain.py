@@ -59,7 +59,9 @@ def test_chain_against_the_oracle(K, save_mode):
     records, exact, strict_bad = [], [], []
 
     def note(label, step, got, a, b, strict=False):
-        r = Record(label, step, rel_err(got, a), rel_l2(got, a), rel_l2(a, b))
+        # end-to-end bar of the chain: the distance between the oracle's two storage precisions (the layers of its
+        # modules are covered one by one in tests/test_gpu_layerwise.py)
+        r = Record(label, step, rel_err(got, a), rel_l2(got, a), rel_l2(a, b), floor=rel_l2(a, b))
         records.append(r)
         # gradients of these small layers: one ReLU gate decided the other way (an activation within rounding of
         # zero) is several per cent of single elements, so their bar is taken in relative L2

@@ -58,11 +58,11 @@ ENVELOPE = {
 }
 
 
-def _check(spec, steps, strict, **kw):
+def _check(spec, steps, strict, deep=False, **kw):
     records, exact = run_side_by_side(spec, steps, **kw)
     print(f"\n[{spec.name}] largest deviations from the kernel-precision oracle\n{format_report(records)}", flush=True)
     assert not exact, exact
-    bad = judge(records, spec, strict)
+    bad = judge(records, spec, strict, deep=deep)
     assert not bad, "\n".join(bad[:40])
 
 
@@ -99,7 +99,10 @@ def test_configs_reduced_batch(idx, n, steps):
     the block below and takes the sums of that block's last batch norm.)"""
     spec = W.config(idx, n=n)
     print(f"case cfg{idx} n={n}", flush=True)
-    _check(spec, steps=steps, strict=False, perturb_bn=False)
+    # the 27- and 150-block modules: noise of the size of a changed summation order reaches order one in their
+    # gradients, so end to end only their forwards and queue states are judged; every layer of them is judged by
+    # itself in tests/test_gpu_layerwise.py
+    _check(spec, steps=steps, strict=False, deep=idx in (2, 5), perturb_bn=False)
 
 
 def test_config4_full_batch():
