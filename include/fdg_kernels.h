@@ -9,6 +9,15 @@
  *
  * All pointers are DEVICE pointers.  Activations are NHWC; "bf16" buffers hold raw bfloat16 (uint16_t
  * storage), "f32" buffers hold float.  Channel counts of bf16 activations must be multiples of 8.
+ *
+ * SUMS ARRAYS.  Per-channel sums that are taken over many workgroups (the batch-norm statistics, the two sums of a
+ * batch-norm backward) live in an opaque "sums array" of fdgk_sums_bytes(c) bytes for c channels (16-byte aligned;
+ * two sums per channel).  Every workgroup adds its partial sum, reduced in a fixed order inside the workgroup, into a
+ * fixed-point total (two 64-bit words) with integer atomics; integer addition is associative, so the totals -- and with
+ * them every result of these entry points -- are the same bits on every run, whatever order the workgroups arrive in
+ * (a partial sum of 2^39 or more, in a network that is blowing up, goes to a floating-point word instead).
+ * A sums array must be ZERO (all bytes) before its producer runs.  fdgk_sums_read synchronises hip_stream and returns
+ * the totals as host doubles: host_out[0..c) = first sum, host_out[c..2c) = second sum.
  * Nothing is allocated; the caller owns every buffer.  `hip_stream` is a hipStream_t (NULL = null
  * stream); calls only enqueue.  Return value: 0 on success, otherwise the hipError_t of the failed
  * check or launch (1 = invalid value for a shape the kernels do not take).
@@ -29,11 +38,13 @@ extern "C" {
 
 /* y = conv(x, w) (+ addend):  y[n,ho,wo,o] = sum_{r,q,i} x[n, ho*s+r-p, wo*s+q-p, i] * w[o,r,q,i].
  *   x_b16 [n,h,w,cip]; w_b16 [co][ksize*ksize][cip]; addend_f32 optional [n,ho,wo,co];
- *   y_f32 / y_b16 optional outputs (at least one);  stats_f32 optional [2*co], zero it first:
- *   stats[o] += sum of bf16(y[..,o]), stats[co+o] += sum of bf16(y[..,o])^2 over all pixels -- the
+ *   y_f32 / y_b16 optional outputs (at least one);  stats_sums optional sums array of co channels, zero it first:
+ *   first sum += sum of bf16(y[..,o]), second sum += sum of bf16(y[..,o])^2 over all pixels -- the
  *   batch-norm statistics of the tensor just written, taken in the epilogue instead of a second pass. */
+size_t fdgk_sums_bytes(int c);
+int fdgk_sums_read(const void* sums, int c, double* host_out, void* hip_stream);
 int fdgk_conv_fwd(const void* x_b16, const void* w_b16, const float* addend_f32, float* y_f32, void* y_b16,
-                  float* stats_f32, int n, int h, int w, int ci, int co, int ksize, int stride, void* hip_stream);
+                  void* stats_sums, int n, int h, int w, int ci, int co, int ksize, int stride, void* hip_stream);
 
 /* Data gradient, the adjoint of fdgk_conv_fwd in x:
  *   dx[n,hi,wi,i] = sum_{o,r,q : hi = ho*s+r-p, wi = wo*s+q-p} dy[n,ho,wo,o] * w[o,r,q,i]  (+ addend)
@@ -47,8 +58,8 @@ int fdgk_conv_dgrad(const void* dy_b16, const void* wt_b16, const float* addend_
 /* The data gradient ending in the ReLU and the batch norm it back-propagates into next (Eq. 8 / Eq. 9 applied to
  * conv o ReLU o BN): with gate_b16 = the ReLU's output and bnx_b16 = the batch norm's input, both [n,h,w,cip],
  *   dx = gate > 0 ? (data gradient + addend) : 0,
- *   gsums[i] += sum over pixels of bf16(dx[..,i]),  gsums[cip+i] += sum of bf16(dx[..,i]) * bnx[..,i]
- * (gsums_f32 [2*cip], zero it first): the two reductions of the batch-norm backward, taken in the output stage of the
+ *   first sum of channel i += sum over pixels of bf16(dx[..,i]),  second sum += sum of bf16(dx[..,i]) * bnx[..,i]
+ * (gsums: a sums array of cip channels, zero it first): the two reductions of the batch-norm backward, taken in the output stage of the
  * convolution instead of a pass of their own.  The wide kernels and the narrow kernel do this: fdgk_conv_dgrad_gates
  * says (1 / 0) whether a shape is covered, fdgk_conv_dgrad_gated returns hipErrorInvalidValue (1) where it is not.  */
 int fdgk_conv_dgrad_gates(int n, int h, int w, int ci, int co, int ksize, int stride);
@@ -59,10 +70,10 @@ int fdgk_conv_dgrad_gates(int n, int h, int w, int ci, int co, int ksize, int st
  * channels in and out, 3x3, stride 1) and 1x1 unit-stride layers that the two-workgroup form of the wide gather kernel
  * runs (input channels a multiple of 64, at most 1024 output channels of the convolution, 300 tiles or more); 1 elsewhere. */
 int fdgk_conv_dgrad_feeding_next(const void* dy_b16, const void* wt_b16, const float* addend_f32, const void* addmask_b16,
-                                 const void* gate_b16, const void* bnx_b16, float* gsums_f32, float* dx_f32, void* dx_b16,
+                                 const void* gate_b16, const void* bnx_b16, void* gsums, float* dx_f32, void* dx_b16,
                                  int n, int h, int w, int ci, int co, int ksize, int stride, void* hip_stream);
 int fdgk_conv_dgrad_gated(const void* dy_b16, const void* wt_b16, const float* addend_f32, const void* gate_b16,
-                          const void* bnx_b16, float* gsums_f32, float* dx_f32, void* dx_b16, int n, int h, int w, int ci,
+                          const void* bnx_b16, void* gsums, float* dx_f32, void* dx_b16, int n, int h, int w, int ci,
                           int co, int ksize, int stride, void* hip_stream);
 
 /* Weight gradient, the adjoint in w, into dw_f32 [co][ksize*ksize][ci]:
@@ -79,39 +90,40 @@ int fdgk_conv_wgrad(const void* x_b16, const void* dy_b16, float* dw_f32, float*
                     int n, int h, int w, int ci, int co, int ksize, int stride, void* hip_stream);
 
 /* Training-mode batch normalisation over the m rows of x_b16 [m, c].
- * stats:  sums_f32[0..c) += sum x, sums_f32[c..2c) += sum x^2   (zero it first).
- * apply:  y = relu?( gamma*(x-mean)/sqrt(var+eps) + beta  [+ res_f32] ), mean/var (biased) from sums. */
-int fdgk_bn_stats(const void* x_b16, float* sums_f32, int m, int c, void* hip_stream);
-int fdgk_bn_apply(const void* x_b16, const float* sums_f32, const float* gamma, const float* beta,
+ * stats:  sums (a sums array of c channels, zero it first): first sum += sum x, second sum += sum x^2.
+ * apply:  y = relu?( gamma*(x-mean)/sqrt(var+eps) + beta  [+ res_f32] ), mean/var (biased) from sums; the variance
+ *         sum x^2 / m - mean^2 is taken in double on the exact totals.                                  */
+int fdgk_bn_stats(const void* x_b16, void* sums, int m, int c, void* hip_stream);
+int fdgk_bn_apply(const void* x_b16, const void* sums, const float* gamma, const float* beta,
                   const float* res_f32, float* y_f32, void* y_b16, int m, int c, float eps, int relu,
                   void* hip_stream);
 
 /* Backward of y = relu(bn(x) [+ ...]) given dy (fp32 if dy_is_f32 else bf16) and the ReLU output
  * mask_b16 (gradient passes where mask > 0):  g = dy*[mask>0];  dbeta = sum g;  dgamma = sum g*xhat;
  *   dx = gamma/sqrt(var+eps) * (g - dbeta/m - xhat*dgamma/m)  (+ addend_f32).
- * scratch_f32 [2c] must be zero on entry.  dx_f32 / dx_b16 optional.                               */
-int fdgk_bn_bwd(const void* dy, int dy_is_f32, const void* mask_b16, const void* x_b16, const float* sums_f32,
-                const float* gamma, float* scratch_f32, const float* addend_f32, float* dx_f32, void* dx_b16,
+ * scratch_sums (a sums array of c channels) must be zero on entry.  dx_f32 / dx_b16 optional.       */
+int fdgk_bn_bwd(const void* dy, int dy_is_f32, const void* mask_b16, const void* x_b16, const void* sums,
+                const float* gamma, void* scratch_sums, const float* addend_f32, float* dx_f32, void* dx_b16,
                 float* dgamma, float* dbeta, int m, int c, float eps, void* hip_stream);
 
 /* fdgk_bn_bwd for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
- * harnesses that forbid hipMalloc): the same computation and the same kernels, but the [2c] sums live in an array
- * that is part of the library's code object (one copy per GPU, 16 KiB, held until the process ends) instead of a
- * caller-provided scratch_f32.  The call allocates and frees nothing.  Limit: c <= fdgk_bn_bwd_static_max_c() (2048);
+ * harnesses that forbid hipMalloc): the same computation and the same kernels, but the scratch sums array lives in an
+ * array that is part of the library's code object (one copy per GPU, 96 KiB, held until the process ends) instead of a
+ * caller-provided scratch_sums.  The call allocates and frees nothing.  Limit: c <= fdgk_bn_bwd_static_max_c() (2048);
  * a larger c (or c % 8 != 0, m <= 0, a required pointer NULL) returns 1 (hipErrorInvalidValue) and enqueues nothing.
  * The array is cleared by a fill kernel on hip_stream at the start of every call and keeps the last call's sums
  * afterwards.  Every call on one GPU shares that GPU's array: calls that may overlap on one GPU (different streams,
  * different host threads) race; order them.  The device that owns hip_stream must be the current device.        */
 int fdgk_bn_bwd_static_max_c(void);
-int fdgk_bn_bwd_static(const void* dy, int dy_is_f32, const void* mask_b16, const void* x_b16, const float* sums_f32,
+int fdgk_bn_bwd_static(const void* dy, int dy_is_f32, const void* mask_b16, const void* x_b16, const void* sums,
                        const float* gamma, const float* addend_f32, float* dx_f32, void* dx_b16, float* dgamma, float* dbeta,
                        int m, int c, float eps, void* hip_stream);
 
 /* The second half of fdgk_bn_bwd for a gradient g_b16 [m, c] that is already gated and whose sums
- * gsums_f32 = [sum g, sum g*x] were left by fdgk_conv_dgrad_gated: dbeta = sum g, dgamma = (sum g*x - mean * sum g) / sqrt(var+eps),
+ * gsums (a sums array: sum g, sum g*x) were left by fdgk_conv_dgrad_gated: dbeta = sum g, dgamma = (sum g*x - mean * sum g) / sqrt(var+eps),
  * dx as in fdgk_bn_bwd.                                                                                */
-int fdgk_bn_bwd_gated(const void* g_b16, const void* x_b16, const float* sums_f32, const float* gamma,
-                      const float* gsums_f32, const float* addend_f32, float* dx_f32, void* dx_b16, float* dgamma,
+int fdgk_bn_bwd_gated(const void* g_b16, const void* x_b16, const void* sums, const float* gamma,
+                      const void* gsums, const float* addend_f32, float* dx_f32, void* dx_b16, float* dgamma,
                       float* dbeta, int m, int c, float eps, void* hip_stream);
 
 /* Momentum SGD with coupled weight decay (Eq. 11 with the optimiser of Section V-A), count % 4 == 0:

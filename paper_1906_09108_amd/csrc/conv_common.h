@@ -94,12 +94,15 @@ __device__ __forceinline__ void store_tile(const GatherConvArgs& a, const f32x4 
     }
   }
   if (a.stats) {
-    // Reduce over pixels: first across the 16 lanes that hold the same 4 channels, then across the waves
-    // of the workgroup in LDS, so that the workgroup ends with one global atomic per channel and value.
-    __shared__ float red[2 * BN];
+    // Reduce over pixels: first across the 16 lanes that hold the same 4 channels, then across the waves of the
+    // workgroup through LDS in wave order (a fixed order: the workgroup's partial sum is reproducible), so that the
+    // workgroup ends with one exact add per channel and value (stat_add).
+    constexpr int NW = 4;                       // waves of the workgroup (256 threads)
+    __shared__ float red[NW][2 * BN];
     __syncthreads();   // the main loop's LDS traffic is over for every wave
-    for (int t = threadIdx.x; t < 2 * BN; t += blockDim.x) red[t] = 0.f;
+    for (int t = threadIdx.x; t < NW * 2 * BN; t += blockDim.x) (&red[0][0])[t] = 0.f;
     __syncthreads();
+    const int wave = threadIdx.x >> 6;
 #pragma unroll
     for (int i = 0; i < FN; ++i)
 #pragma unroll
@@ -112,14 +115,16 @@ __device__ __forceinline__ void store_tile(const GatherConvArgs& a, const f32x4 
         }
         if ((lane & 15) == 0) {
           const int cl = c_wave + i * 16 + 4 * (lane >> 4) + v;
-          atomicAdd(&red[cl], x1);
-          atomicAdd(&red[BN + cl], x2);
+          red[wave][cl] = x1;
+          red[wave][BN + cl] = x2;
         }
       }
     __syncthreads();
     for (int t = threadIdx.x; t < 2 * BN; t += blockDim.x) {
       const int c = c_tile + (t % BN);
-      if (c < a.Co) atomicAdd(a.stats + (size_t)(blockIdx.x % kStatReplicas) * a.stats_rep_stride + (t / BN) * a.Co + c, red[t]);
+      if (c < a.Co)
+        stat_add(a.stats + (size_t)(blockIdx.x % kStatReplicas) * a.stats_rep_stride, a.Co, t / BN, c,
+                 (red[0][t] + red[1][t]) + (red[2][t] + red[3][t]));
     }
   }
 }
@@ -304,7 +309,7 @@ __device__ __forceinline__ void store_rows32(const GatherConvArgs& a, const f32x
 #pragma unroll
           for (int w = 0; w < PARKW; ++w) sum += park[(size_t)((w * PERIOD + k) * 64 + l) * 8 + which * 4 + e];
       }
-      atomicAdd(a.stats + (size_t)(blockIdx.x % kStatReplicas) * a.stats_rep_stride + which * a.Co + c, sum);
+      stat_add(a.stats + (size_t)(blockIdx.x % kStatReplicas) * a.stats_rep_stride, a.Co, which, c, sum);
     }
   }
 }

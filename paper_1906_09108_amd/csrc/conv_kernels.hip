@@ -191,6 +191,8 @@ __device__ __forceinline__ void transpose8x8(const uint4 (&r)[8], uint4 (&o)[8])
 struct WgradLaunch {
   int chunks_per_split;
   int ci_tiles;
+  float* partial;        // when set: pixel split z, contraction part wk store their block at partial + (z * WK + wk) * split_stride
+  size_t split_stride;   // (plain stores: a second kernel adds the parts in a fixed order); else fp32 atomics into dw
 };
 
 template <int BM, int BN, int WM, int WN, int WK>
@@ -303,6 +305,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(WgradArgs a, WgradLaunc
 
   // D[co][ci]: lane holds co = 4*(lane>>4)+v, ci = lane&15
   if (chunk_lo >= chunk_hi) return;
+  float* part = L.partial ? L.partial + (size_t)(blockIdx.z * WK + wk) * L.split_stride : nullptr;
 #pragma unroll
   for (int i = 0; i < FA; ++i)
 #pragma unroll
@@ -312,46 +315,76 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(WgradArgs a, WgradLaunc
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
         const int co = co0 + wm * TM + i * 16 + 4 * (lane >> 4) + v;
-        if (co < a.Co) atomicAdd(a.dw + ((size_t)co * a.ntaps + tapi) * a.Ci + ci, acc[i][j][v]);
+        if (co >= a.Co) continue;
+        const size_t o = ((size_t)co * a.ntaps + tapi) * a.Ci + ci;
+        if (part) part[o] = acc[i][j][v];
+        else atomicAdd(a.dw + o, acc[i][j][v]);
       }
     }
 }
 
-template <int BM, int BN, int WM, int WN, int WK>
-static hipError_t run_wgrad(const WgradArgs& a, hipStream_t s) {
+// pixel splits of the kernel above for a shape, and the parts (splits x contraction parts) its partial sums take
+template <int BM, int BN, int WK>
+static void wgrad_plan(const WgradArgs& a, int& splits, int& chunks_per_split, int& parts) {
   constexpr int BK = 32 * WK * (WK == 1 ? 2 : 1);
   const int Mtot = a.N * a.OH * a.OW;
   const int co_tiles = (a.Co + BM - 1) / BM, ci_tiles = (a.Ci + BN - 1) / BN;
   const int total_chunks = (Mtot + BK - 1) / BK;
   const int base = co_tiles * ci_tiles * a.ntaps;
-  int splits = (1024 + base - 1) / base;
+  splits = (1024 + base - 1) / base;
   if (splits > total_chunks) splits = total_chunks;
   if (splits < 1) splits = 1;
+  chunks_per_split = (total_chunks + splits - 1) / splits;
+  splits = (total_chunks + chunks_per_split - 1) / chunks_per_split;   // every split has at least one chunk
+  parts = splits * WK;
+}
+hipError_t launch_wgrad_reduce(float* dw, const float* partial, size_t elems, int parts, int overwrite, hipStream_t s);
+
+template <int BM, int BN, int WM, int WN, int WK>
+static hipError_t run_wgrad(const WgradArgs& a, hipStream_t s) {
+  const int co_tiles = (a.Co + BM - 1) / BM, ci_tiles = (a.Ci + BN - 1) / BN;
+  int splits, parts;
   WgradLaunch L;
-  L.chunks_per_split = (total_chunks + splits - 1) / splits;
+  wgrad_plan<BM, BN, WK>(a, splits, L.chunks_per_split, parts);
   L.ci_tiles = ci_tiles;
-  splits = (total_chunks + L.chunks_per_split - 1) / L.chunks_per_split;
+  const size_t elems = (size_t)a.Co * a.ntaps * a.Ci;
+  // with scratch memory every part stores its block and a second kernel adds the parts in a fixed order (the result is
+  // the same on every run); without it the parts add into dw with fp32 atomics
+  const bool stored = a.scratch && elems % 4 == 0 && a.scratch_bytes >= (size_t)parts * elems * sizeof(float);
+  L.partial = stored ? a.scratch : nullptr;
+  L.split_stride = elems;
+  if (!stored && a.overwrite) {   // atomics only add
+    hipError_t e = launch_fill_f32(a.dw, elems, 0.f, s);
+    if (e != hipSuccess) return e;
+  }
   dim3 grid(co_tiles, ci_tiles * a.ntaps, splits);
   static char name[64];
   if (!name[0]) snprintf(name, sizeof(name), "conv_wgrad_kernel<%d, %d, %d, %d, %d>", BM, BN, WM, WN, WK);
   note_kernel(name);
   hipLaunchKernelGGL((conv_wgrad_kernel<BM, BN, WM, WN, WK>), grid, dim3(256), 0, s, a, L);
-  return hipGetLastError();
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || !stored) return e;
+  return launch_wgrad_reduce(a.dw, a.scratch, elems, parts, a.overwrite, s);
+}
+
+// bytes of scratch with which the kernel above stores its parts instead of adding them with atomics
+static size_t generic_wgrad_scratch_bytes(const WgradArgs& a) {
+  int splits, cps, parts;
+  if (a.Co <= 64 && a.Cx <= 64) wgrad_plan<32, 32, 4>(a, splits, cps, parts);
+  else if (a.Cx <= 32) wgrad_plan<128, 32, 1>(a, splits, cps, parts);
+  else wgrad_plan<128, 128, 1>(a, splits, cps, parts);
+  const size_t elems = (size_t)a.Co * a.ntaps * a.Ci;
+  return elems % 4 == 0 ? (size_t)parts * elems * sizeof(float) : 0;
 }
 
 hipError_t launch_conv_wgrad(const WgradArgs& a, hipStream_t s) {
   if (a.Co % 8 != 0 || a.Cx % 8 != 0 || a.Ci > a.Cx || a.ntaps < 1 || a.ntaps > 9 || a.N * a.OH * a.OW <= 0)
     return hipErrorInvalidValue;
-  static const bool old_wide = getenv("FDG_WGRAD_160") != nullptr;   // A/B switch for measurements
-  if (conv_wgrad128_applies(a) && !(old_wide && conv_wgrad_wide_applies(a))) return launch_conv_wgrad128(a, s);
-  if (conv_wgrad_tall_applies(a) && !(old_wide && conv_wgrad_wide_applies(a))) return launch_conv_wgrad_tall(a, s);
+  if (conv_wgrad128_applies(a)) return launch_conv_wgrad128(a, s);
+  if (conv_wgrad_tall_applies(a)) return launch_conv_wgrad_tall(a, s);
   if (conv_wgrad_wide_applies(a)) return launch_conv_wgrad_wide(a, s);
   if (conv_wgrad_narrow_applies(a) && a.scratch && a.scratch_bytes >= conv_wgrad_narrow_scratch_bytes(a))
     return launch_conv_wgrad_narrow(a, s);
-  if (a.overwrite) {   // the kernels below only add (atomics)
-    hipError_t e = launch_fill_f32(a.dw, (size_t)a.Co * a.ntaps * a.Ci, 0.f, s);
-    if (e != hipSuccess) return e;
-  }
   if (a.Co <= 64 && a.Cx <= 64) return run_wgrad<32, 32, 1, 1, 4>(a, s);
   if (a.Cx <= 32) return run_wgrad<128, 32, 4, 1, 1>(a, s);   // many output channels from few inputs (WRN's 16 -> 160)
   return run_wgrad<128, 128, 2, 2, 1>(a, s);
@@ -361,7 +394,7 @@ hipError_t launch_conv_wgrad(const WgradArgs& a, hipStream_t s) {
 // geometry of the three passes of one convolution
 // ------------------------------------------------------------------------------------------------
 hipError_t conv_forward(const ConvShape& c, const bf16_t* x, const bf16_t* w, const float* addend, float* out_f32,
-                        bf16_t* out_b16, float* stats, hipStream_t s, int stats_rep_stride) {
+                        bf16_t* out_b16, stat_t* stats, hipStream_t s, int stats_rep_stride) {
   GatherConvArgs a{};
   a.stats_rep_stride = stats_rep_stride;
   a.in = x; a.w = w; a.addend = addend; a.addmask = nullptr; a.out_f32 = out_f32; a.out_b16 = out_b16; a.stats = stats;
@@ -380,7 +413,7 @@ hipError_t conv_forward(const ConvShape& c, const bf16_t* x, const bf16_t* w, co
 }
 
 static hipError_t conv_dgrad_impl(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
-                                  const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, float* gsums, float* out_f32,
+                                  const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, stat_t* gsums, float* out_f32,
                                   bf16_t* out_b16, hipStream_t s, bool stats_f32 = false, int rep_stride = 0);
 
 hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
@@ -405,7 +438,7 @@ bool conv_dgrad_feeds_next(const ConvShape& c) {
 }
 
 hipError_t conv_dgrad_feeding_next(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
-                                   const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, float* gsums, float* out_f32,
+                                   const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, stat_t* gsums, float* out_f32,
                                    bf16_t* out_b16, hipStream_t s, int gsums_rep_stride) {
   if (!gate || !bnx || !gsums || !out_f32 || !conv_dgrad_feeds_next(c)) return hipErrorInvalidValue;
   return conv_dgrad_impl(c, dy, wt, addend, addmask, gate, bnx, gsums, out_f32, out_b16, s, /*stats_f32=*/true, gsums_rep_stride);
@@ -420,14 +453,14 @@ bool conv_dgrad_gates(const ConvShape& c) {
 }
 
 hipError_t conv_dgrad_gated(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend, const bf16_t* gate,
-                            const bf16_t* bnx, float* gsums, float* out_f32, bf16_t* out_b16, hipStream_t s,
+                            const bf16_t* bnx, stat_t* gsums, float* out_f32, bf16_t* out_b16, hipStream_t s,
                             int gsums_rep_stride) {
   if (!gate || !bnx || !gsums || !conv_dgrad_gates(c)) return hipErrorInvalidValue;
   return conv_dgrad_impl(c, dy, wt, addend, nullptr, gate, bnx, gsums, out_f32, out_b16, s, false, gsums_rep_stride);
 }
 
 static hipError_t conv_dgrad_impl(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
-                                  const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, float* gsums, float* out_f32,
+                                  const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, stat_t* gsums, float* out_f32,
                                   bf16_t* out_b16, hipStream_t s, bool stats_f32, int rep_stride) {
   GatherConvArgs a{};
   a.stats_rep_stride = rep_stride;
@@ -524,7 +557,7 @@ size_t conv_wgrad_scratch_bytes(const ConvShape& c_in) {
     for (int q = 0; q < 3; ++q) a.tap[r * 3 + q] = pack_tap(r - 1, q - 1, 0);
   a.Cx = c.Cip;
   if (conv_wgrad_narrow_applies(a)) return conv_wgrad_narrow_scratch_bytes(a);
-  if (!(conv_wgrad_wide_applies(a) || conv_wgrad128_applies(a) || conv_wgrad_tall_applies(a))) return 0;
+  if (!(conv_wgrad_wide_applies(a) || conv_wgrad128_applies(a) || conv_wgrad_tall_applies(a))) return generic_wgrad_scratch_bytes(a);
   // room for the partial sums of the pixel splits: 8 of them, or as many as it takes the 160 x 160 kernel to fill
   // the chip when a layer has few blocks (160 -> 160: 9 blocks per filter)
   size_t splits = 8;

@@ -132,7 +132,7 @@ __device__ __forceinline__ void narrow_store(const GatherConvArgs& a, const f32x
 }
 
 // The per-channel sums a workgroup gathered over its tiles: over the 16 lanes that hold the same 4 channels, then one
-// slot per wave in LDS, then over the waves, then one atomic per channel and value into this workgroup's copy.
+// slot per wave in LDS, then over the waves (a fixed order), then one exact add per channel and value into this workgroup's copy.
 template <int NB, int WN, int CO>
 __device__ __forceinline__ void narrow_flush_sums(const GatherConvArgs& a, const float (&s1)[NB][4], const float (&s2)[NB][4],
                                                   int wave, int lane) {
@@ -161,7 +161,7 @@ __device__ __forceinline__ void narrow_flush_sums(const GatherConvArgs& a, const
       float sum = 0.f;
 #pragma unroll
       for (int w = 0; w < WM; ++w) sum += red[owner * WM + w][which][cl];
-      atomicAdd(a.stats + (size_t)(blockIdx.x % kStatReplicas) * a.stats_rep_stride + which * CO + c, sum);
+      stat_add(a.stats + (size_t)(blockIdx.x % kStatReplicas) * a.stats_rep_stride, CO, which, c, sum);
     }
   }
 }
@@ -556,8 +556,6 @@ bool plan_wgrad_narrow(const WgradArgs& a, NarrowWgradPlan& P) {
 }  // namespace
 
 bool conv_narrow_applies(const GatherConvArgs& a) {
-  static const bool off = getenv("FDG_NO_NARROW") != nullptr || getenv("FDG_NO_NARROW_CONV") != nullptr;   // A/B switch for measurements
-  if (off) return false;
   const bool stem = a.Ci == 8 && (a.Co == 16 || a.Co == 32 || a.Co == 64);   // 3 input channels stored as 8
   if (!stem && a.Ci != 16 && a.Ci != 32 && a.Ci != 64) return false;
   if ((!stem && a.Co != a.Ci) || a.w_rows != a.Co || a.Kw != 9 * a.Ci) return false;
@@ -583,8 +581,6 @@ hipError_t launch_conv_narrow(const GatherConvArgs& a, hipStream_t s) {
 }
 
 bool conv_wgrad_narrow_applies(const WgradArgs& a) {
-  static const bool off = getenv("FDG_NO_NARROW") != nullptr || getenv("FDG_NO_NARROW_WGRAD") != nullptr;   // A/B switch for measurements
-  if (off) return false;
   if (a.Co != 16 && a.Co != 32 && a.Co != 64) return false;
   const bool same = a.Ci == a.Co && a.Cx == a.Co;                  // C -> C
   if (!same && !wgrad_narrow_is_stem(a)) return false;              // or the stem: 3 (stored as 8) -> C

@@ -872,10 +872,9 @@ template <int BN>
 static hipError_t run_patch_rows(const GatherConvArgs& a, hipStream_t s) {
   // 256-pixel tiles where 128-pixel tiles need more than one round of workgroups and the larger ones still fill the chip
   {
-    static const bool off = getenv("FDG_PATCH_128") != nullptr;   // A/B switch for measurements
     const int Mtot = a.N * a.OH * a.OW, n_tiles = (a.Co + BN - 1) / BN;
     const int t128 = (Mtot + 127) / 128 * n_tiles, t256 = (Mtot + 255) / 256 * n_tiles;
-    if (!off && t128 > 256 && t256 >= 224) {
+    if (t128 > 256 && t256 >= 224) {
       if (a.Ci % 64 != 0) return run_patch256<BN, 384, 3, true>(a, s);
       return 256 + 2 * a.Wi + 2 <= 320 ? run_patch256<BN, 320, 3, false>(a, s) : run_patch256<BN, 384, 3, false>(a, s);
     }
@@ -948,14 +947,10 @@ static hipError_t run_wide_pair(const GatherConvArgs& a, hipStream_t s) {
 
 // The two-workgroup form runs this layer (and with it the output stage that can take the sums of the fp32 values).
 bool conv_gather_pair_applies(const GatherConvArgs& a) {
-  static const bool no_patch = getenv("FDG_NO_PATCH") != nullptr;
-  if (a.nclass > 1 || a.Co % 160 == 0 || a.Ci % 64 != 0 || !conv_gather_wide_applies(a) || (conv_patch_applies(a) && !no_patch)) return false;
+  if (a.nclass > 1 || a.Co % 160 == 0 || a.Ci % 64 != 0 || !conv_gather_wide_applies(a) || conv_patch_applies(a)) return false;
   const int steps = a.ntaps * ((a.Ci + 63) / 64);
   const long tiles = (long)((a.N * a.OH * a.OW + 127) / 128) * ((a.Co + 127) / 128);
-  static const bool no_short = getenv("FDG_NO_SHORT_K") != nullptr;   // A/B switch for measurements
-  static const int pair_steps = getenv("FDG_PAIR_STEPS") ? atoi(getenv("FDG_PAIR_STEPS")) : 16;     // for measurements
-  static const int pair_tiles = getenv("FDG_PAIR_TILES") ? atoi(getenv("FDG_PAIR_TILES")) : 300;
-  return !no_short && steps <= pair_steps && tiles >= pair_tiles;
+  return steps <= 16 && tiles >= 300;   // a short contraction over more tiles than compute units
 }
 
 template <int BN, int STAGES>
@@ -970,8 +965,7 @@ hipError_t launch_conv_gather_wide(const GatherConvArgs& a, hipStream_t s) {
   }
   if (!conv_gather_wide_applies(a) || a.N * a.OH * a.OW <= 0) return hipErrorInvalidValue;
   if (a.stats && a.stats_f32 && !conv_gather_pair_applies(a)) return hipErrorInvalidValue;   // only that form takes the sums of the fp32 values
-  static const bool no_patch = getenv("FDG_NO_PATCH") != nullptr;
-  if (conv_patch_applies(a) && !no_patch) return a.Co % 160 == 0 ? run_patch_rows<160>(a, s) : run_patch_rows<128>(a, s);
+  if (conv_patch_applies(a)) return a.Co % 160 == 0 ? run_patch_rows<160>(a, s) : run_patch_rows<128>(a, s);
   // A short contraction (a 1x1 convolution: at most 16 steps per tile) over more tiles than compute units: two stages
   // instead of four are 75 KB of LDS, so two workgroups share a compute unit, one's output stage runs beside the
   // other's loads and main loop, and 257 .. 512 tiles take one round instead of two.
@@ -1183,19 +1177,57 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(float4* __restrict__ 
   }
 }
 
+// The same for many parts of a small array: 16 lanes share a float4 of dw, lane q adds the parts q, q + 16, ... and the
+// sixteen partial sums are added through LDS in lane order (a fixed order).
+__global__ __launch_bounds__(256) void wgrad_reduce_lanes_kernel(float4* __restrict__ dw, const float4* __restrict__ partial,
+                                                                 size_t n4, int parts, size_t stride4, int overwrite) {
+  __shared__ float4 sh[16][16];
+  const int e = threadIdx.x & 15, q = threadIdx.x >> 4;
+  const size_t i = (size_t)blockIdx.x * 16 + e;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (i < n4) {
+#pragma unroll 4
+    for (int k = q; k < parts; k += 16) {
+      const float4 p = partial[(size_t)k * stride4 + i];
+      s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+    }
+  }
+  sh[q][e] = s;
+  __syncthreads();
+  if (q == 0 && i < n4) {
+    float4 t = overwrite ? make_float4(0.f, 0.f, 0.f, 0.f) : dw[i];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) { t.x += sh[j][e].x; t.y += sh[j][e].y; t.z += sh[j][e].z; t.w += sh[j][e].w; }
+    dw[i] = t;
+  }
+}
+
+hipError_t launch_wgrad_reduce(float* dw, const float* partial, size_t elems, int parts, int overwrite, hipStream_t s) {
+  if (elems % 4 != 0 || parts < 1) return hipErrorInvalidValue;
+  const size_t n4 = elems / 4;
+  if (parts >= 32) {
+    hipLaunchKernelGGL(wgrad_reduce_lanes_kernel, dim3((unsigned)((n4 + 15) / 16)), dim3(256), 0, s, reinterpret_cast<float4*>(dw),
+                       reinterpret_cast<const float4*>(partial), n4, parts, n4, overwrite);
+    return hipGetLastError();
+  }
+  size_t blocks = (n4 + 255) / 256;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, s, reinterpret_cast<float4*>(dw),
+                     reinterpret_cast<const float4*>(partial), n4, parts, n4, overwrite);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------------------
 // Weight gradient, 128 x 128 blocks on 32x32x16 MFMAs
 // ------------------------------------------------------------------------------------------------
-// Same wave layout as the forward kernels: wave_m = wave & 1 owns 64 of the block's 128 output channels (all
-// 128 input channels: 2 x 4 accumulator blocks), wk = wave >> 1 one 32-pixel half of every 64-pixel chunk, and
-// the two halves are added through LDS at the end.  (Letting every wave own the whole block and a quarter of
-// the pixels would read each staged byte exactly once, but 256 accumulator registers leave the compiler no
-// room and it spills.)  Tiles are [pixel][128 channels] (256-byte rows) read with the transposing LDS load;
-// the 32-byte slot of a row is XORed with 2 * (pixel & 3) so that the 4 pixels x 2 channel blocks a half wave
-// reads in one pass cover all banks.  The x source of a row advances by a constant per chunk (the launcher
-// requires Hi == stride * OH and OW | 64), and whether the row falls into the padding repeats with a short
-// period over the chunks, so row validity is a per-lane bit mask indexed by chunk phase.  Operand reads run
-// one half step ahead of the MFMAs, pinned with scheduling barriers as in the patch kernel.
+// A block is 128 output channels x 128 input channels of one tap.  (Letting every wave own the whole block and a part of
+// the pixels would read each staged byte exactly once, but 256 accumulator registers leave the compiler no room and it
+// spills: the waves split the block, see the kernel.)  Tiles are [pixel][128 channels] (256-byte rows) read with the
+// transposing LDS load; the 32-byte slot of a row is XORed with 2 * (pixel & 3) so that the 4 pixels x 2 channel blocks
+// a half wave reads in one pass cover all banks.  The x source of a row advances by a constant per chunk (the launcher
+// requires Hi == stride * OH and OW | 64, or the flat form), and whether the row falls into the padding repeats with a
+// short period over the chunks, so row validity is a per-lane bit mask indexed by chunk phase.  Operand reads run one
+// half step ahead of the MFMAs, pinned with scheduling barriers as in the patch kernel.
 struct Wgrad128Launch {
   int co_tiles, ci_tiles, splits, chunks_per_split;
   float* partial;        // when set: split s stores its block at partial + s * split_stride
@@ -1206,272 +1238,7 @@ struct Wgrad128Launch {
   long long a_step, b_step;   // bytes from one chunk to the next in dy and in x
 };
 
-template <int STAGES>
-__global__ __launch_bounds__(256) void conv_wgrad128_kernel(WgradArgs a, Wgrad128Launch L) {
-  constexpr int BC = 128, BKP = 64, ROWB = BC * 2, PART = BKP * ROWB, JP = 4, NJ = 2 * JP;
-  constexpr int FA = 2, FB = 4, NF = FA + FB, NM = FA * FB;   // fragments and MFMAs per 16-pixel step
-  static_assert(STAGES >= 3 && (STAGES - 2) * NJ < 64, "pipeline depth / vmcnt range");
-  static_assert(STAGES * 2 * PART >= 4 * 16 * 1024, "room for the exchange of the partial blocks");
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // STAGES * 2 * PART
-
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wave_m = wave & 1, wk = wave >> 1;
-
-  // Every block streams its channels of both operands over all its pixels, and what an XCD's blocks have in
-  // common is fetched once into its L2.  So the blocks of an XCD are consecutive in the order (split, output
-  // tile, input tile, tap): one pixel split (or two), few channel tiles, all their taps.  Dealt round robin,
-  // every XCD would fetch both operands in full: 8 x 21 MB per launch.
-  int t = xcd_consecutive(blockIdx.x, gridDim.x);
-  const int tapi = t % a.ntaps; t /= a.ntaps;
-  const int ci_t = t % L.ci_tiles; t /= L.ci_tiles;
-  const int co_t = t % L.co_tiles;
-  const int split = t / L.co_tiles;
-  const int co0 = co_t * BC, ci0 = ci_t * BC;
-  const int tp = a.tap[tapi];
-  const int dh = (tp & 0xff) - 8, dw = ((tp >> 8) & 0xff) - 8;
-  const int total_chunks = (a.N * a.OH * a.OW) / BKP;
-  const int chunk_lo = split * L.chunks_per_split;
-  const int n = min(total_chunks, chunk_lo + L.chunks_per_split) - chunk_lo;
-  if (n <= 0) return;
-
-  // ---- per-thread DMA sources: instruction j of this wave covers pixel rows 4*(4j+wave) .. +3 ----
-  const char* aptr[JP];
-  const char* bptr[JP];
-  unsigned bmask[JP];
-#pragma unroll
-  for (int j = 0; j < JP; ++j) {
-    const int r = 4 * (4 * j + wave) + (lane >> 4), up = lane & 15;
-    const int u = 2 * ((up >> 1) ^ (2 * (r & 3))) + (up & 1);
-    const int m = chunk_lo * BKP + r;
-    aptr[j] = reinterpret_cast<const char*>(a.dy) + ((size_t)m * a.Co + co0 + u * 8) * 2;
-    const int ow = m % a.OW, t2 = m / a.OW, oh = t2 % a.OH, nimg = t2 / a.OH;
-    const int iw = ow * a.stride + dw;
-    const bool colok = (unsigned)iw < (unsigned)a.Wi;
-    bptr[j] = reinterpret_cast<const char*>(a.x) +
-              ((((long long)nimg * a.Hi + oh * a.stride + dh) * a.Wi + iw) * a.Cx + ci0 + u * 8) * 2;
-    unsigned mask = 0;
-    int ohq = oh;
-    for (int q = 0; q < L.period; ++q) {
-      if (colok && (unsigned)(ohq * a.stride + dh) < (unsigned)a.Hi) mask |= 1u << q;
-      ohq += L.d_oh;
-      if (ohq >= a.OH) ohq -= a.OH;
-    }
-    bmask[j] = mask;
-  }
-  const char* zero = reinterpret_cast<const char*>(g_zero_word);
-
-  int issue_phase = 0;   // (chunk being issued) mod period
-  auto issue_one = [&](int d, int c) {   // piece d of chunk c (relative to chunk_lo)
-    unsigned char* stage = smem + (size_t)(c % STAGES) * (2 * PART);
-    if (d < JP) {
-      dma16(aptr[d] + (long long)c * L.a_step, stage + (64 * (4 * d + wave)) * 16);
-    } else {
-      const int j = d - JP;
-      const bool ok = (bmask[j] >> issue_phase) & 1u;
-      // select per 32-bit half: two conditional moves instead of a branch around the address computation
-      const uint64_t pa = (uint64_t)(bptr[j] + (long long)c * L.b_step), pz = (uint64_t)zero;
-      const uint32_t lo = ok ? (uint32_t)pa : (uint32_t)pz, hi = ok ? (uint32_t)(pa >> 32) : (uint32_t)(pz >> 32);
-      dma16((const char*)(((uint64_t)hi << 32) | lo), stage + PART + (64 * (4 * j + wave)) * 16);
-    }
-  };
-  auto issue_done = [&]() { issue_phase = issue_phase + 1 == L.period ? 0 : issue_phase + 1; };
-
-  f32x16 acc[FA][FB];
-#pragma unroll
-  for (int i = 0; i < FA; ++i)
-#pragma unroll
-    for (int j = 0; j < FB; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-  // ---- operand reads: lane group g = lane >> 4 takes channels 16*(g&1).. of a 32-channel block and pixels
-  //      8*(g>>1) .. +7 of the 16-pixel step (two transposing reads of 4 pixels each) ----
-  int boff[FB], aoff[FA];   // byte offset inside a tile of a 32-channel block, step 0 of this wave's pixel half
-  {
-    const int g = lane >> 4, i16 = lane & 15;
-    const int prow = 32 * wk + 8 * (g >> 1) + (i16 >> 2);
-    const int x = 2 * ((i16 >> 2) & 3);
-#pragma unroll
-    for (int f = 0; f < FB; ++f) boff[f] = prow * ROWB + (i16 & 3) * 8 + (((2 * f + (g & 1)) ^ x) * 32);
-#pragma unroll
-    for (int f = 0; f < FA; ++f) aoff[f] = prow * ROWB + (i16 & 3) * 8 + (((2 * (FA * wave_m + f) + (g & 1)) ^ x) * 32);
-  }
-  // fragment f < FA: dy block 2*wave_m.. (rows of D); f >= FA: x block f - FA (columns of D).
-  // The transposing read is issued as inline assembly: the compiler treats its builtin as a possible LDS
-  // store and puts a wait for ALL outstanding direct-to-LDS loads in front of every one of them, which
-  // serialises the pipeline.  So the waits are explicit here: wait_frags() ties an lgkmcnt(0) to the registers
-  // of a fragment set, and landing of the loads is covered by the vmcnt wait before each barrier.
-  const unsigned lds0 = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)smem);
-  v4s16 flo[2][NF], fhi[2][NF];
-  auto read_one = [&](auto set_tag, auto idx_tag, int c, int ks) {
-    constexpr int S = decltype(set_tag)::value, IDX = decltype(idx_tag)::value;
-    // issue order = the order the MFMAs need them: A0, B0, B1, B2, B3, A1
-    constexpr int POS = IDX >> 1, H = IDX & 1;
-    constexpr int F = POS == 0 ? 0 : (POS == NF - 1 ? 1 : POS + 1);
-    int off;
-    if constexpr (F < FA) off = aoff[F]; else off = PART + boff[F - FA];
-    const unsigned addr = lds0 + (unsigned)(c % STAGES) * (2 * PART) + off + ks * 16 * ROWB;
-    v4s16& v = H == 0 ? flo[S][F] : fhi[S][F];
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "i"(H * 4 * ROWB));
-  };
-  // LDS reads return in order, so "the first m reads of this set have landed" is lgkmcnt <= (reads of the set
-  // still to come) + (reads of the other set issued meanwhile).  before_mma(set, K, N) states that for MFMA K
-  // and ties the wait to the registers that become valid, so the MFMA cannot move above it.
-  auto before_mma = [&](auto set_tag, auto k_tag, auto n_tag) {
-    constexpr int S = decltype(set_tag)::value, K = decltype(k_tag)::value, N = decltype(n_tag)::value;
-    static_assert(FA == 2 && FB == 4 && N >= 0 && N <= 15, "fragment order A0 B0 B1 B2 B3 A1");
-    if constexpr (K == 0) {
-      v4s16 &l0 = flo[S][0], &h0 = fhi[S][0], &l1 = flo[S][FA], &h1 = fhi[S][FA];
-      asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(l0), "+v"(h0), "+v"(l1), "+v"(h1) : "n"(N));
-    } else if constexpr (K >= 1 && K <= 3) {
-      v4s16 &l0 = flo[S][FA + K], &h0 = fhi[S][FA + K];
-      asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(l0), "+v"(h0) : "n"(N));
-    } else if constexpr (K == 4) {
-      v4s16 &l0 = flo[S][1], &h0 = fhi[S][1];
-      asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(l0), "+v"(h0) : "n"(N));
-    }
-  };
-  auto frag = [&](auto set_tag, int f) {
-    constexpr int S = decltype(set_tag)::value;
-    typedef short v8s16 __attribute__((ext_vector_type(8)));
-    const v8s16 both = __builtin_shufflevector(flo[S][f], fhi[S][f], 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, both);
-  };
-  auto mma_one = [&](auto set_tag, auto k_tag) {
-    constexpr int K = decltype(k_tag)::value;
-    acc[K / FB][K % FB] = mfma32(frag(set_tag, K / FB), frag(set_tag, FA + K % FB), acc[K / FB][K % FB]);
-  };
-
-  // prologue: chunks 0 .. STAGES-2 in flight, chunk 0 visible, the fragments of its first step in set 0
-#pragma unroll
-  for (int p = 0; p < STAGES - 1; ++p)
-    if (p < n) {
-#pragma unroll
-      for (int d = 0; d < NJ; ++d) issue_one(d, p);
-      issue_done();
-    }
-  if (n >= STAGES - 1) wait_vmcnt<(STAGES - 2) * NJ>();
-  else if (n == 2) wait_vmcnt<NJ>();
-  else wait_vmcnt<0>();
-  asm volatile("" ::: "memory");
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
-  using set0 = std::integral_constant<int, 0>;
-  using set1 = std::integral_constant<int, 1>;
-  static_for<2 * NF>([&](auto idx) { read_one(set0{}, idx, 0, 0); });
-
-  // One chunk = two half steps of NM (MFMA, piece) slots.  First half: MFMAs of set 0, reads of the second step
-  // into set 1; after slot 1 barrier c+1 (chunk c+1 visible; everybody done reading chunk c-1).  Second half:
-  // MFMAs of set 1, first-step reads of chunk c+1 into set 0.  The NJ loads of chunk c+STAGES-1 (into the stage
-  // of chunk c-1) go out one every other slot from the barrier to the end of the chunk: in a burst they fill the
-  // address queue and the wave stalls, MFMAs included.  AHEAD = chunks issued beyond c+1 at the barrier.
-  static_assert(2 * NF <= 2 * (NM - 2) && 2 + 2 * (NJ - 1) < 2 * NM + 1, "slots of a chunk");
-  auto step = [&](auto next_tag, auto issue_tag, auto ahead_tag, int c) {
-    constexpr bool NEXT = decltype(next_tag)::value, ISSUE = decltype(issue_tag)::value;
-    constexpr int AHEAD = decltype(ahead_tag)::value;
-    auto issue_at = [&](auto s_tag) {   // global slot 0 .. 2 NM - 1: load d after slot 2 + 2 d (the last one shares slot 2 NM - 1)
-      constexpr int SL = decltype(s_tag)::value;
-      if constexpr (ISSUE) {
-        if constexpr (SL >= 2 && (SL - 2) % 2 == 0 && (SL - 2) / 2 < NJ) issue_one((SL - 2) / 2, c + STAGES - 1);
-        if constexpr (SL == 2 * NM - 1 && 2 + 2 * (NJ - 1) >= 2 * NM) issue_one(NJ - 1, c + STAGES - 1);
-      }
-    };
-    static_for<NM>([&](auto k) {
-      constexpr int K = decltype(k)::value;
-      // 12 reads per set, two per slot: set 1 is filled in slots 0..5 of this half
-      before_mma(set0{}, k, std::integral_constant<int, 8>{});
-      mma_one(set0{}, k);
-      if constexpr (2 * K < 2 * NF) {
-        read_one(set1{}, std::integral_constant<int, 2 * K>{}, c, 1);
-        read_one(set1{}, std::integral_constant<int, 2 * K + 1>{}, c, 1);
-      }
-      if constexpr (NEXT && K == 1) {
-        wait_vmcnt<AHEAD * NJ>();
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-      }
-      issue_at(std::integral_constant<int, K>{});
-      __builtin_amdgcn_sched_barrier(0);
-    });
-    static_for<NM>([&](auto k) {
-      constexpr int K = decltype(k)::value;
-      // set 0 of the next chunk is filled in slots 2..7 of this half (only when there is a next chunk)
-      constexpr int LEFT = K == 0 ? 8 : (K == 1 ? 6 : (K == 2 ? 4 : (K == 3 ? 2 : 0)));
-      constexpr int NEWER = (NEXT && K > 2) ? 2 * (K - 2) : 0;
-      before_mma(set1{}, k, std::integral_constant<int, (K <= 4 ? LEFT + NEWER : 15)>{});
-      mma_one(set1{}, k);
-      if constexpr (NEXT) {
-        if constexpr (K >= 2 && 2 * (K - 2) < 2 * NF) {
-          read_one(set0{}, std::integral_constant<int, 2 * (K - 2)>{}, c + 1, 0);
-          read_one(set0{}, std::integral_constant<int, 2 * (K - 2) + 1>{}, c + 1, 0);
-        }
-      }
-      issue_at(std::integral_constant<int, NM + K>{});
-      __builtin_amdgcn_sched_barrier(0);
-    });
-    if constexpr (ISSUE) issue_done();
-  };
-  using yes = std::true_type;
-  using no = std::false_type;
-  {
-    int c = 0;
-    for (; c + STAGES - 1 < n; ++c) step(yes{}, yes{}, std::integral_constant<int, STAGES - 3>{}, c);
-    // tail: nothing left to issue; chunks beyond c+1 still in flight: n - c - 2
-    static_for<STAGES - 2>([&](auto r_tag) {
-      constexpr int AH = STAGES - 3 - decltype(r_tag)::value;   // STAGES-3, ..., 0
-      if (c + 1 < n && n - c - 2 == AH) {
-        step(yes{}, no{}, std::integral_constant<int, AH>{}, c);
-        ++c;
-      }
-    });
-    step(no{}, no{}, std::integral_constant<int, 0>{}, c);   // c == n - 1
-  }
-
-  // ---- add the two pixel halves: wave (wave_m, wk) keeps block row wk of its two and receives its partner's ----
-  wait_vmcnt<0>();
-  __syncthreads();
-  f32x4* mine = reinterpret_cast<f32x4*>(smem) + (size_t)wave * 1024;
-  const f32x4* theirs = reinterpret_cast<const f32x4*>(smem) + (size_t)(wave ^ 2) * 1024;
-  f32x16 keep[FB];
-#pragma unroll
-  for (int j = 0; j < FB; ++j) {
-    const f32x16 give = wk == 0 ? acc[1][j] : acc[0][j];
-    keep[j] = wk == 0 ? acc[0][j] : acc[1][j];
-#pragma unroll
-    for (int g = 0; g < 4; ++g)
-      mine[(j * 4 + g) * 64 + lane] = f32x4{give[4 * g], give[4 * g + 1], give[4 * g + 2], give[4 * g + 3]};
-  }
-  __syncthreads();
-#pragma unroll
-  for (int j = 0; j < FB; ++j)
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const f32x4 p = theirs[(j * 4 + g) * 64 + lane];
-      keep[j][4 * g] += p[0]; keep[j][4 * g + 1] += p[1]; keep[j][4 * g + 2] += p[2]; keep[j][4 * g + 3] += p[3];
-    }
-  // D block: lane holds column ci = 32 j + (lane & 31), rows co = 8 (v >> 2) + 4 (lane >> 5) + (v & 3) of the block row
-  float* dst = L.partial ? L.partial + (size_t)split * L.split_stride : a.dw;
-  const int mode = (L.partial || (L.splits == 1 && a.overwrite)) ? 0 : (L.splits > 1 ? 1 : 2);   // store / atomic add / owned read-modify-write
-  const int ntaps = a.ntaps, Ci = a.Ci;
-  const int co_base = co0 + 64 * wave_m + 32 * wk + 4 * (lane >> 5);
-#pragma unroll
-  for (int j = 0; j < FB; ++j) {
-    const int ci = ci0 + 32 * j + (lane & 31);
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int co = co_base + 8 * (v >> 2) + (v & 3);
-      float* o = dst + ((size_t)co * ntaps + tapi) * Ci + ci;
-      const float val = keep[j][v];
-      if (mode == 0) *o = val;
-      else if (mode == 1) atomicAdd(o, val);
-      else *o += val;
-    }
-  }
-}
-
-// The same 128 x 128 blocks with EIGHT waves, two per SIMD.  Four waves issue the direct-to-LDS loads, the LDS reads
+// EIGHT waves, two per SIMD.  Four waves would issue the direct-to-LDS loads, the LDS reads
 // and the MFMAs of a step one after the other and end up at the sum of the three times; LDS reads of four waves also
 // top out near 80 bytes per clock against 150 with eight.  Here wave (wm, wn, wk) owns 64 output channels x 64 input
 // channels (2 x 2 accumulator blocks: 64 registers, so two waves fit a SIMD easily) and two of the four 16-pixel
@@ -1496,7 +1263,11 @@ __global__ __launch_bounds__(512) void conv_wgrad128w8_kernel(WgradArgs a, Wgrad
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave & 1, wn = (wave >> 1) & 1, wk = wave >> 2;
 
-  int t = xcd_consecutive(blockIdx.x, gridDim.x);   // see conv_wgrad128_kernel
+  // Every block streams its channels of both operands over all its pixels, and what an XCD's blocks have in
+  // common is fetched once into its L2.  So the blocks of an XCD are consecutive in the order (split, output
+  // tile, input tile, tap): one pixel split (or two), few channel tiles, all their taps.  Dealt round robin,
+  // every XCD would fetch both operands in full: 8 x 21 MB per launch.
+  int t = xcd_consecutive(blockIdx.x, gridDim.x);
   const int tapi = t % a.ntaps; t /= a.ntaps;
   const int ci_t = t % L.ci_tiles; t /= L.ci_tiles;
   const int co_t = t % L.co_tiles;
@@ -1764,10 +1535,7 @@ hipError_t launch_conv_wgrad128(const WgradArgs& a, hipStream_t s) {
   constexpr size_t lds = (size_t)STAGES * 2 * 64 * 256;
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad128_kernel<STAGES>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    configured = true;
+    configured = true;   // (the two forms of the kernel are configured where they are launched)
   }
   const int total_chunks = a.N * a.OH * a.OW / 64;
   Wgrad128Launch L;
@@ -1797,7 +1565,6 @@ hipError_t launch_conv_wgrad128(const WgradArgs& a, hipStream_t s) {
   L.b_step = (long long)d_oh_full * a.stride * a.Wi * a.Cx * 2;
   L.step_w = 0;
   const bool flat = 64 % a.OW != 0 || a.OH > 32;   // conv_wgrad128_applies has checked that the flat form applies then
-  static const bool four_waves = getenv("FDG_WGRAD_4W") != nullptr;   // A/B switch for measurements
   if (flat) {
     L.period = wgrad128_flat_period(a);
     if (L.period <= 0) return hipErrorInvalidValue;
@@ -1813,7 +1580,7 @@ hipError_t launch_conv_wgrad128(const WgradArgs& a, hipStream_t s) {
     }
     note_kernel("conv_wgrad128w8_kernel<5, flat>");
     hipLaunchKernelGGL((conv_wgrad128w8_kernel<STAGES, true>), dim3(tiles * L.splits), dim3(512), lds, s, a, L);
-  } else if (!four_waves) {
+  } else {
     static bool configured8 = false;
     if (!configured8) {
       hipError_t e8 = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad128w8_kernel<STAGES, false>),
@@ -1823,9 +1590,6 @@ hipError_t launch_conv_wgrad128(const WgradArgs& a, hipStream_t s) {
     }
     note_kernel("conv_wgrad128w8_kernel<5>");
     hipLaunchKernelGGL((conv_wgrad128w8_kernel<STAGES, false>), dim3(tiles * L.splits), dim3(512), lds, s, a, L);
-  } else {
-  note_kernel("conv_wgrad128_kernel<5>");
-  hipLaunchKernelGGL((conv_wgrad128_kernel<STAGES>), dim3(tiles * L.splits), dim3(256), lds, s, a, L);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || !L.partial) return e;

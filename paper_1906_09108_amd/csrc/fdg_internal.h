@@ -18,11 +18,55 @@ __host__ __device__ static inline int pack_tap(int dh, int dw, int kofs) { retur
 // Rows m enumerate an output grid [N, OH, OW]; the output pixel of row (n, oh, ow) is
 // (n, oh*out_stride + ooh, ow*out_stride + oow) in a tensor [N, OHf, OWf, Co].  Forward convolution,
 // stride-1 data gradient and each parity class of a stride-2 data gradient are all of this form.
-// Per-channel sums are added with one atomic request per workgroup; hundreds of workgroups onto one cache line
-// serialise at the memory side (6 - 11 us per launch for the narrow layers).  A sums array may therefore exist in
-// kStatReplicas copies, rep_stride floats apart: workgroup b adds into copy b % kStatReplicas and whoever reads the
-// sums adds the copies (in a fixed order).  rep_stride = 0: a single copy.
+// Per-channel sums (batch-norm statistics, the two sums of a batch-norm backward) are taken over many workgroups.
+// Each workgroup adds ITS fp32 partial sum, reduced in a fixed order inside the workgroup, into the total -- and the
+// total is kept EXACTLY, in 64-bit fixed point: the partial s is split into hi = rint(s * 2^11) and
+// lo = rint((s - hi * 2^-11) * 2^62) (exact for 2^-39 <= |s| < 2^39; smaller partials are rounded to 2^-62) and both
+// words are added with integer atomics.  Integer addition is associative, so the total does not depend on the order in
+// which workgroups arrive: two runs on the same input give the same bits, which no fp32 atomic sum does.  Up to 4096
+// partials fit.  A partial of 2^39 (5.5e11) or more -- a network that is blowing up -- goes to a third word, a double
+// added with a floating-point atomic: still a sum, no longer order independent.
+// A sums array for C channels is stat_t[3][2][C] (word, which of the two sums, channel), zero before the producers run;
+// value = big + hi * 2^-11 + lo * 2^-62.
+// Hundreds of workgroups onto one cache line serialise at the memory side (6 - 11 us per launch for the narrow
+// layers), so an array may exist in kStatReplicas copies, rep_stride stat_t elements apart: workgroup b adds into copy
+// b % kStatReplicas and whoever reads the sums adds the copies (integers again).  rep_stride = 0: a single copy.
 constexpr int kStatReplicas = 8;
+typedef long long stat_t;
+constexpr int kStatWords = 3;                                   // stat_t per sum: hi, lo, big (a double)
+inline size_t stat_elems(size_t channels) { return 2 * channels * kStatWords; }   // stat_t of a sums array
+
+#if defined(__HIPCC__)
+// total[which][c] += s, for the sums array of C channels starting at `stats`
+__device__ __forceinline__ void stat_add(stat_t* stats, int C, int which, int c, float s) {
+  const double d = (double)s;
+  stat_t* p = stats + (size_t)which * C + c;
+  if (fabs(d) < 0x1p39) {
+    const double h = rint(d * 0x1p11);
+    const long long hi = (long long)h, lo = (long long)rint((d - h * 0x1p-11) * 0x1p62);
+    atomicAdd(reinterpret_cast<unsigned long long*>(p), (unsigned long long)hi);
+    atomicAdd(reinterpret_cast<unsigned long long*>(p + 2 * (size_t)C), (unsigned long long)lo);
+  } else {
+    atomicAdd(reinterpret_cast<double*>(p + 4 * (size_t)C), d);
+  }
+}
+__device__ __forceinline__ double stat_value(long long hi, long long lo, long long big) {
+  return __builtin_bit_cast(double, big) + ((double)hi * 0x1p-11 + (double)lo * 0x1p-62);
+}
+// the total of channel c, copies added
+__device__ __forceinline__ double stat_load(const stat_t* stats, int C, int which, int c, int rep_stride) {
+  const stat_t* p = stats + (size_t)which * C + c;
+  long long hi = p[0], lo = p[2 * (size_t)C];
+  double big = __builtin_bit_cast(double, p[4 * (size_t)C]);
+  if (rep_stride > 0)
+    for (int r = 1; r < kStatReplicas; ++r) {
+      const stat_t* q = p + (size_t)r * rep_stride;
+      hi += q[0]; lo += q[2 * (size_t)C];
+      big += __builtin_bit_cast(double, q[4 * (size_t)C]);
+    }
+  return stat_value(hi, lo, __builtin_bit_cast(long long, big));
+}
+#endif
 
 struct GatherConvArgs {
   const bf16_t* in;      // [N, Hi, Wi, Ci] bf16, Ci % 8 == 0
@@ -31,12 +75,12 @@ struct GatherConvArgs {
   const bf16_t* addmask; // optional: addend counts only where this bf16 tensor (output indexing) is > 0
   float* out_f32;        // optional fp32 output
   bf16_t* out_b16;       // optional bf16 output
-  float* stats;          // optional [2*Co]: += per-channel sum and sum of squares of the bf16-rounded output
+  stat_t* stats;         // optional sums array of Co channels: += per-channel sum and sum of squares of the bf16-rounded output
   // Data gradient that ends in the ReLU and batch norm it back-propagates into next (wide kernels only):
   const bf16_t* gate;    // optional (output indexing): the output is kept where gate > 0 and is zero elsewhere
   const bf16_t* bnx;     // optional (output indexing), with stats: stats[Co + c] += sum of output * bnx instead of
                          // the squares -- with stats[c] the two sums the batch-norm backward needs
-  int stats_rep_stride;  // floats between the copies of stats (0: one copy)
+  int stats_rep_stride;  // stat_t elements between the copies of stats (0: one copy)
   int stats_f32;         // with bnx, narrow / generic output stage: the sums are of the fp32 values, not of the bf16 output
   int N, Hi, Wi, Ci;
   int OH, OW, in_stride;
@@ -92,7 +136,7 @@ struct ConvShape {
 // stats (optional, [2*Co], pre-zeroed): += per-channel sum and sum of squares of the bf16-rounded result,
 // i.e. the batch-norm statistics of the tensor just produced
 hipError_t conv_forward(const ConvShape& c, const bf16_t* x, const bf16_t* w, const float* addend, float* out_f32,
-                        bf16_t* out_b16, float* stats, hipStream_t s, int stats_rep_stride = 0);
+                        bf16_t* out_b16, stat_t* stats, hipStream_t s, int stats_rep_stride = 0);
 // dx[N,Hi,Wi,Cip] = conv^T(dy[N,Ho,Wo,Co], wt[Cip][T][Co]) (+ addend, optionally only where addmask > 0)
 hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                       const bf16_t* addmask, float* out_f32, bf16_t* out_b16, hipStream_t s);
@@ -103,11 +147,11 @@ hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, co
 // carry the two sums of that layer's last batch norm (conv_dgrad_feeding_next).
 bool conv_dgrad_feeds_next(const ConvShape& c);
 hipError_t conv_dgrad_feeding_next(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
-                                   const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, float* gsums, float* out_f32,
+                                   const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, stat_t* gsums, float* out_f32,
                                    bf16_t* out_b16, hipStream_t s, int gsums_rep_stride = 0);
 bool conv_dgrad_gates(const ConvShape& c);
 hipError_t conv_dgrad_gated(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend, const bf16_t* gate,
-                            const bf16_t* bnx, float* gsums, float* out_f32, bf16_t* out_b16, hipStream_t s,
+                            const bf16_t* bnx, stat_t* gsums, float* out_f32, bf16_t* out_b16, hipStream_t s,
                             int gsums_rep_stride = 0);
 // dw[Co][T][Ci] (+)= sum over pixels of dy * x.  overwrite = false: accumulated into dw (fp32 atomics where the
 // pixel dimension is split), dw zeroed by the caller;  overwrite = true: dw is written, whatever it held.
@@ -118,17 +162,17 @@ hipError_t conv_wgrad(const ConvShape& c, const bf16_t* x, const bf16_t* dy, flo
 size_t conv_wgrad_scratch_bytes(const ConvShape& c);
 
 // Batch-norm pieces on [M, C] NHWC tensors (C % 8 == 0, C <= 2048).
-// sums = [sum_c | sumsq_c] fp32, pre-zeroed; accumulated with atomics.
-hipError_t launch_bn_stats(const bf16_t* x, float* sums, int M, int C, hipStream_t s);
+// sums = a sums array of C channels (sum, sum of squares), pre-zeroed; accumulated exactly (see stat_t).
+hipError_t launch_bn_stats(const bf16_t* x, stat_t* sums, int M, int C, hipStream_t s);
 
 struct BnApplyArgs {
   const bf16_t* x;       // [M, C]
-  const float* sums;     // [2C] of x
+  const stat_t* sums;    // sums array of x
   const float* gamma;    // [C]
   const float* beta;     // [C]
   const float* res_f32;  // optional fp32 residual [M, C]
   const bf16_t* x2;      // optional second normalised operand (projection shortcut) [M, C]
-  const float* sums2;    // its sums, gamma, beta
+  const stat_t* sums2;   // its sums, gamma, beta
   const float* gamma2;
   const float* beta2;
   float* out_f32;        // optional
@@ -140,19 +184,19 @@ struct BnApplyArgs {
   int M, C;
   float eps, momentum;
   int relu;
-  int rep_stride;        // floats between the copies of sums and of sums2 (0: one copy)
+  int rep_stride;        // stat_t elements between the copies of sums and of sums2 (0: one copy)
 };
 hipError_t launch_bn_apply(const BnApplyArgs& a, hipStream_t s);
 
-// Backward: g = dy * [mask > 0];  bsums = [sum g | sum g*xhat] (pre-zeroed, atomics)
+// Backward: g = dy * [mask > 0];  bsums = sums array [sum g | sum g*xhat] (pre-zeroed)
 struct BnBwdArgs {
   const void* dy;        // [M, C] fp32 or bf16 (dy_is_f32)
   int dy_is_f32;
   const bf16_t* mask;    // [M, C] ReLU output (or pre-activation sign carrier); required
   const bf16_t* x;       // [M, C] the BN input saved by the forward
-  const float* sums;     // forward sums of x
+  const stat_t* sums;    // forward sums of x
   const float* gamma;    // snapshot gamma
-  float* bsums;          // [2C]
+  stat_t* bsums;         // sums array of C channels
   const float* addend;   // optional fp32 [M, C] added to dx (apply only)
   float* out_f32;        // optional dx
   bf16_t* out_b16;       // optional dx
@@ -162,8 +206,8 @@ struct BnBwdArgs {
   float eps;
   int dy_gated;          // apply only: dy is already zero where the gate is closed (mask is not read)
   int raw_sums;          // apply only: bsums holds sum g and sum g*x (not g*xhat), as a gated data gradient leaves them
-  int rep_stride;        // floats between the copies of sums (0: one copy)
-  int brep_stride;       // apply only: floats between the copies of bsums (0: one copy); the reduce pass adds into copy 0
+  int rep_stride;        // stat_t elements between the copies of sums (0: one copy)
+  int brep_stride;       // apply only: stat_t elements between the copies of bsums (0: one copy); the reduce pass adds into copy 0
 };
 hipError_t launch_bn_bwd_reduce(const BnBwdArgs& a, hipStream_t s);
 hipError_t launch_bn_bwd_apply(const BnBwdArgs& a, hipStream_t s);

@@ -61,7 +61,7 @@ struct Plan {
   size_t P = 0;                // internal parameter arena (elements, multiple of 4)
   size_t small_off = 0, small_count = 0;
   size_t stat_floats = 0;      // 2 * sum of BN channels
-  int stat_rep = 0;            // floats between the copies of a sums array: stat_floats where the narrow kernels run
+  int stat_rep = 0;            // stat_t elements between the copies of the sums arrays: all of them where the narrow kernels run
                                // (hundreds of small workgroups add into the sums), else 0 = a single copy
   size_t warena_elems = 0;     // bf16 elements of one slot's weight arena
   size_t emit_blocks = 0;
@@ -277,7 +277,7 @@ bool build_plan(const fdg_module_desc* desc, int save_mode, Plan& p, fdg_status*
   if (p.P >= (1ull << 31) || p.warena_elems >= (1ull << 32) || p.maxE >= (1ull << 31)) { *why = FDG_ERR_UNSUPPORTED; return false; }
   for (const ConvInfo& ci : p.convs) p.emit_blocks += emit_blocks_for(ci.sh.Co, ci.sh.Cip, ci.sh.T);
   for (const ConvInfo& ci : p.convs)
-    if (conv_dgrad_feeds_next(ci.sh)) p.stat_rep = (int)p.stat_floats;
+    if (conv_dgrad_feeds_next(ci.sh)) p.stat_rep = (int)(p.stat_floats * kStatWords);
   const size_t stat_copies = p.stat_rep ? kStatReplicas : 1;
   // workspace layout
   size_t o = 0;
@@ -285,7 +285,7 @@ bool build_plan(const fdg_module_desc* desc, int save_mode, Plan& p, fdg_status*
   p.o_params = take(p.P * 4);
   p.o_mom = take(p.P * 4);
   p.o_grads = take(p.P * 4);
-  p.o_bsums = take(p.stat_floats * 4 * stat_copies);   // the copies are stat_floats apart
+  p.o_bsums = take(p.stat_floats * kStatWords * sizeof(stat_t) * stat_copies);   // exact sums (stat_t pairs), copy after copy
   p.o_running = take(p.stat_floats * 4);
   p.o_table = take(p.convs.size() * sizeof(WeightEmitEntry));
   {  // one slot; the intermediates follow the snapshots inside it, or form a region of their own (replay)
@@ -299,7 +299,7 @@ bool build_plan(const fdg_module_desc* desc, int save_mode, Plan& p, fdg_status*
     p.s_small = stake(p.small_count * 4);
     if (p.is_top) p.s_labels = stake((size_t)N * 4);
     if (p.replay) p.s_xcopy = stake((size_t)N * desc->c_in * desc->h_in * desc->w_in * 4);
-    p.s_sums = itake(p.stat_floats * 4 * stat_copies);
+    p.s_sums = itake(p.stat_floats * kStatWords * sizeof(stat_t) * stat_copies);
     p.s_xin = itake((size_t)N * desc->h_in * desc->w_in * p.Cp_in * 2);
     p.s_acts = itake(act_bytes);
     if (p.is_top) {
@@ -404,7 +404,7 @@ struct fdg_module {
   float* params() const { return reinterpret_cast<float*>(ws + p.o_params); }
   float* mom() const { return reinterpret_cast<float*>(ws + p.o_mom); }
   float* grads() const { return reinterpret_cast<float*>(ws + p.o_grads); }
-  float* bsums() const { return reinterpret_cast<float*>(ws + p.o_bsums); }
+  stat_t* bsums(const BnInfo& b) const { return reinterpret_cast<stat_t*>(ws + p.o_bsums) + b.stat_off * kStatWords; }
   float* running() const { return reinterpret_cast<float*>(ws + p.o_running); }
   char* slot(int64_t seq) const { return ws + p.o_slots + p.slot_bytes * (size_t)(seq % (p.d.delay + 1)); }
   float* S(int i) const { return reinterpret_cast<float*>(ws + p.o_S[i]); }
@@ -438,7 +438,7 @@ struct SlotView {
   float* small() const { return reinterpret_cast<float*>(base + m->p.s_small); }
   // snapshot of a small parameter given its offset in the parameter arena
   float* snap(size_t arena_off) const { return small() + (arena_off - m->p.small_off); }
-  float* sums(const BnInfo& b) const { return reinterpret_cast<float*>(inter + m->p.s_sums) + b.stat_off; }
+  stat_t* sums(const BnInfo& b) const { return reinterpret_cast<stat_t*>(inter + m->p.s_sums) + b.stat_off * kStatWords; }
   bf16_t* xin() const { return reinterpret_cast<bf16_t*>(inter + m->p.s_xin); }
   bf16_t* act(size_t off) const { return reinterpret_cast<bf16_t*>(inter + m->p.s_acts + off); }
   float* pooled() const { return reinterpret_cast<float*>(inter + m->p.s_pooled); }
@@ -485,7 +485,7 @@ inline double conv_out_elems(const ConvShape& c) { return (double)c.N * c.Ho() *
 inline double conv_w_elems(const ConvShape& c) { return (double)c.Co * c.T * c.Cip; }
 
 hipError_t mconv_forward(const fdg_module* m, const ConvInfo& c, const bf16_t* x, const bf16_t* w, const float* addend,
-                         float* out_f32, bf16_t* out_b16, float* stats, hipStream_t s) {
+                         float* out_f32, bf16_t* out_b16, stat_t* stats, hipStream_t s) {
   const double bytes = 2 * conv_in_elems(c.sh) + 2 * conv_w_elems(c.sh) +
                        conv_out_elems(c.sh) * ((addend ? 4 : 0) + (out_f32 ? 4 : 0) + (out_b16 ? 2 : 0));
   ProfScope ps(m, PC_CONV_FWD, conv_flops(c.sh), bytes, s);
@@ -495,8 +495,6 @@ hipError_t mconv_forward(const fdg_module* m, const ConvInfo& c, const bf16_t* x
 }
 // ---- the side stream of the weight gradients (see SideStream) ----
 bool side_create(SideStream& sd) {
-  static const bool off = getenv("FDG_NO_OVERLAP") != nullptr;   // A/B switch for measurements
-  if (off) return true;
   bool ok = hipStreamCreateWithFlags(&sd.stream, hipStreamNonBlocking) == hipSuccess;
   ok = ok && hipEventCreateWithFlags(&sd.ready, hipEventDisableTiming) == hipSuccess;
   ok = ok && hipEventCreateWithFlags(&sd.joined, hipEventDisableTiming) == hipSuccess;
@@ -598,7 +596,7 @@ hipError_t bn_backward(const fdg_module* m, const SlotView& v, const BnInfo& b, 
   BnBwdArgs a{};
   a.dy = dy; a.dy_is_f32 = dy_f32 ? 1 : 0; a.mask = mask; a.x = x; a.sums = v.sums(b);
   a.gamma = v.snap(b.gamma_off);
-  a.bsums = m->bsums() + b.stat_off;
+  a.bsums = m->bsums(b);
   a.addend = addend; a.out_f32 = out_f32; a.out_b16 = out_b16;
   a.dgamma = m->grads() + b.gamma_off; a.dbeta = m->grads() + b.beta_off;
   a.M = b.M; a.C = b.C; a.eps = m->p.d.bn_eps;
@@ -621,7 +619,7 @@ hipError_t bn_backward_after_gated_dgrad(const fdg_module* m, const SlotView& v,
   BnBwdArgs a{};
   a.dy = g; a.dy_is_f32 = 0; a.mask = nullptr; a.x = x; a.sums = v.sums(b);
   a.gamma = v.snap(b.gamma_off);
-  a.bsums = m->bsums() + b.stat_off;
+  a.bsums = m->bsums(b);
   a.addend = addend; a.out_f32 = out_f32; a.out_b16 = out_b16;
   a.dgamma = m->grads() + b.gamma_off; a.dbeta = m->grads() + b.beta_off;
   a.M = b.M; a.C = b.C; a.eps = m->p.d.bn_eps;
@@ -640,7 +638,7 @@ hipError_t bn_backward_fed_from_above(const fdg_module* m, const SlotView& v, co
   BnBwdArgs a{};
   a.dy = g; a.dy_is_f32 = 1; a.mask = nullptr; a.x = x; a.sums = v.sums(b);
   a.gamma = v.snap(b.gamma_off);
-  a.bsums = m->bsums() + b.stat_off;
+  a.bsums = m->bsums(b);
   a.out_b16 = out_b16;
   a.dgamma = m->grads() + b.gamma_off; a.dbeta = m->grads() + b.beta_off;
   a.M = b.M; a.C = b.C; a.eps = m->p.d.bn_eps;
@@ -657,13 +655,12 @@ hipError_t bn_backward_fed_from_above(const fdg_module* m, const SlotView& v, co
 hipError_t dgrad_relu_bn_backward(const fdg_module* m, const SlotView& v, const ConvInfo& c, const bf16_t* dy, const bf16_t* wt,
                                   const float* dgrad_addend, const BnInfo& b, const bf16_t* gate, const bf16_t* x, bf16_t* g,
                                   const float* bn_addend, float* out_f32, bf16_t* out_b16, hipStream_t s) {
-  static const bool unfused = getenv("FDG_NO_GATED_DGRAD") != nullptr;   // A/B switch for measurements
-  if (!unfused && conv_dgrad_gates(c.sh) && b.C == c.sh.Cip) {
+  if (conv_dgrad_gates(c.sh) && b.C == c.sh.Cip) {
     if (hipError_t e = side_wait_readers(m, g, s); e != hipSuccess) return e;
     {
       const double bytes = 2 * conv_out_elems(c.sh) + 2 * conv_w_elems(c.sh) + conv_in_elems(c.sh) * ((dgrad_addend ? 4 : 0) + 2 + 2 + 2);
       ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c.sh), bytes, s);
-      const hipError_t e = conv_dgrad_gated(c.sh, dy, wt, dgrad_addend, gate, x, m->bsums() + b.stat_off, nullptr, g, s,
+      const hipError_t e = conv_dgrad_gated(c.sh, dy, wt, dgrad_addend, gate, x, m->bsums(b), nullptr, g, s,
                                             m->p.stat_rep);
       ps.label(c.sh);
       if (e != hipSuccess) return e;
@@ -694,7 +691,8 @@ const BnInfo* closing_bn(const Plan& p, const SlotView& v, const LayerPlan& L, c
 fdg_status forward_pass(fdg_module* m, const SlotView& v, const float* x_dev, float* y_dev, bool replayed, hipStream_t s) {
   const Plan& p = m->p;
   const int N = p.d.n;
-  if (p.stat_floats) FDG_TRY(launch_fill_zero(v.sums(p.bns[0]), align_up(p.stat_floats * 4 * (p.stat_rep ? kStatReplicas : 1), 16), s));
+  if (p.stat_floats)
+    FDG_TRY(launch_fill_zero(v.sums(p.bns[0]), p.stat_floats * kStatWords * sizeof(stat_t) * (p.stat_rep ? kStatReplicas : 1), s));
   // module input: fp32 NCHW -> fp32 NHWC stream + bf16 NHWC copy (kept for the backward)
   int cur = 0;
   FDG_TRY(launch_nchw_to_nhwc(x_dev, (p.d.c_in % 8 == 0) ? m->S(cur) : nullptr, v.xin(), N, p.d.c_in, p.d.h_in * p.d.w_in,
@@ -760,7 +758,7 @@ fdg_status forward_pass(fdg_module* m, const SlotView& v, const float* x_dev, fl
         shortcut = m->TP();
       }
       // the block output is the next layer's BN input when that layer is pre-activated: take its sums here
-      float* next_stats = nullptr;
+      stat_t* next_stats = nullptr;
       if (li + 1 < p.L.size() && (p.L[li + 1].kind == FDG_BASIC_PREACT || p.L[li + 1].kind == FDG_HEAD_PREACT))
         next_stats = v.sums(p.bns[p.L[li + 1].bn[0]]);
       FDG_TRY(mconv_forward(m, c2, t_o2, v.W(c2), shortcut, m->S(nxt), v.act(L.out_b), next_stats, s));
@@ -908,7 +906,6 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
   if (m->trace && !p.is_top)
     FDG_TRY(hipMemcpyAsync(m->trace + p.tr_bwd[p.L.size()], m->G(cur), (size_t)N * p.out_h * p.out_w * p.out_c * 4,
                            hipMemcpyDeviceToDevice, s));
-  static const bool no_feed = getenv("FDG_NO_GATED_DGRAD") != nullptr || getenv("FDG_NO_FEED") != nullptr;   // A/B switches for measurements
   bool fed = false;   // G(cur) came from the layer above already gated by this layer's output, with this layer's
                       // last batch norm's two sums in bsums
   for (int li = (int)p.L.size() - 1; li >= 0; --li) {
@@ -963,12 +960,12 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
         // backward: the ReLU gate and the two sums of the batch norm.
         const bf16_t* bnx = nullptr;
         const BnInfo* bb = li > 0 ? closing_bn(p, v, p.L[li - 1], &bnx) : nullptr;
-        if (!no_feed && bb && bb->C == c1.sh.Cip && conv_dgrad_feeds_next(c1.sh)) {
+        if (bb && bb->C == c1.sh.Cip && conv_dgrad_feeds_next(c1.sh)) {
           FDG_TRY(side_wait_readers(m, m->GB(nxt), s));
           const double bytes = 2 * conv_out_elems(c1.sh) + 2 * conv_w_elems(c1.sh) + conv_in_elems(c1.sh) * (4 + 2 + 2 + 2 + 4 + 2);
           ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c1.sh), bytes, s);
           const hipError_t e = conv_dgrad_feeding_next(c1.sh, m->T(0), v.Wt(c1), m->G(cur), t_y, in_b, bnx,
-                                                       m->bsums() + bb->stat_off, m->G(nxt), m->GB(nxt), s, p.stat_rep);
+                                                       m->bsums(*bb), m->G(nxt), m->GB(nxt), s, p.stat_rep);
           ps.label(c1.sh);
           FDG_TRY(e);
           fed = true;
@@ -1003,12 +1000,12 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
         // the output of the layer below and take the two sums of that layer's last batch norm
         const bf16_t* bnx = nullptr;
         const BnInfo* bb = li > 0 ? closing_bn(p, v, p.L[li - 1], &bnx) : nullptr;
-        if (!no_feed && bb && bb->C == c1.sh.Cip && conv_dgrad_feeds_next(c1.sh)) {
+        if (bb && bb->C == c1.sh.Cip && conv_dgrad_feeds_next(c1.sh)) {
           FDG_TRY(side_wait_readers(m, m->GB(nxt), s));
           const double bytes = 2 * conv_out_elems(c1.sh) + 2 * conv_w_elems(c1.sh) + conv_in_elems(c1.sh) * (4 + 2 + 2 + 2 + 4 + 2);
           ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c1.sh), bytes, s);
           const hipError_t e = conv_dgrad_feeding_next(c1.sh, m->T(0), v.Wt(c1), m->G(cur), t_y, in_b, bnx,
-                                                       m->bsums() + bb->stat_off, m->G(nxt), m->GB(nxt), s, p.stat_rep);
+                                                       m->bsums(*bb), m->G(nxt), m->GB(nxt), s, p.stat_rep);
           ps.label(c1.sh);
           FDG_TRY(e);
           fed = true;

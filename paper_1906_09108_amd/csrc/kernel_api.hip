@@ -3,7 +3,9 @@
 #include "../../include/fdg_kernels.h"
 #include "fdg_internal.h"
 
+#include <cstring>
 #include <mutex>
+#include <vector>
 
 using namespace fdg;
 
@@ -17,24 +19,24 @@ bool conv_shape(ConvShape& c, int n, int h, int w, int ci, int co, int ksize, in
 inline hipStream_t st(void* s) { return static_cast<hipStream_t>(s); }
 
 // ---- the scratch of the entry point that allocates nothing (fdgk_bn_bwd_static) ----
-// One array per GPU, held until the process ends: the two per-channel sums of a batch-norm backward for up to
-// kStaticMaxC channels.  In host code the array's name is only a stand-in; its device address is looked up once per
+// One array per GPU, held until the process ends: the two per-channel sums (exact, two 64-bit words each) of a batch-norm
+// backward for up to kStaticMaxC channels: 96 KiB.  In host code the array's name is only a stand-in; its device address is looked up once per
 // device (with that device current) and that pointer is what kernels, fills and copies are given.
 constexpr int kStaticMaxC = 2048;
 constexpr int kStaticMaxDevices = 64;
-static __device__ __align__(256) float scratch[2 * kStaticMaxC];
+static __device__ __align__(256) stat_t scratch[2 * kStaticMaxC * kStatWords];
 std::mutex g_scratch_lock;
-float* g_scratch_ptr[kStaticMaxDevices] = {};
+stat_t* g_scratch_ptr[kStaticMaxDevices] = {};
 
 // the current device's copy of `scratch`, or nullptr with *err set
-float* static_scratch(hipError_t* err) {
+stat_t* static_scratch(hipError_t* err) {
   int dev = -1;
   *err = hipGetDevice(&dev);
   if (*err != hipSuccess) return nullptr;
   if (dev < 0 || dev >= kStaticMaxDevices) { *err = hipErrorInvalidDevice; return nullptr; }
   std::lock_guard<std::mutex> hold(g_scratch_lock);
   if (!g_scratch_ptr[dev]) {
-    float* p = nullptr;
+    stat_t* p = nullptr;
     *err = hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch));
     if (*err != hipSuccess || !p) {
       if (*err == hipSuccess) *err = hipErrorInvalidSymbol;
@@ -50,11 +52,11 @@ float* static_scratch(hipError_t* err) {
 extern "C" {
 
 int fdgk_conv_fwd(const void* x_b16, const void* w_b16, const float* addend_f32, float* y_f32, void* y_b16,
-                  float* stats_f32, int n, int h, int w, int ci, int co, int ksize, int stride, void* hip_stream) {
+                  void* stats_sums, int n, int h, int w, int ci, int co, int ksize, int stride, void* hip_stream) {
   ConvShape c;
   if (!x_b16 || !w_b16 || (!y_f32 && !y_b16) || !conv_shape(c, n, h, w, ci, co, ksize, stride)) return (int)hipErrorInvalidValue;
   return (int)conv_forward(c, static_cast<const bf16_t*>(x_b16), static_cast<const bf16_t*>(w_b16), addend_f32, y_f32,
-                           static_cast<bf16_t*>(y_b16), stats_f32, st(hip_stream));
+                           static_cast<bf16_t*>(y_b16), static_cast<stat_t*>(stats_sums), st(hip_stream));
 }
 
 int fdgk_conv_dgrad(const void* dy_b16, const void* wt_b16, const float* addend_f32, const void* addmask_b16,
@@ -67,26 +69,26 @@ int fdgk_conv_dgrad(const void* dy_b16, const void* wt_b16, const float* addend_
 }
 
 int fdgk_conv_dgrad_gated(const void* dy_b16, const void* wt_b16, const float* addend_f32, const void* gate_b16,
-                          const void* bnx_b16, float* gsums_f32, float* dx_f32, void* dx_b16, int n, int h, int w, int ci,
+                          const void* bnx_b16, void* gsums, float* dx_f32, void* dx_b16, int n, int h, int w, int ci,
                           int co, int ksize, int stride, void* hip_stream) {
   ConvShape c;
-  if (!dy_b16 || !wt_b16 || !gate_b16 || !bnx_b16 || !gsums_f32 || (!dx_f32 && !dx_b16) ||
+  if (!dy_b16 || !wt_b16 || !gate_b16 || !bnx_b16 || !gsums || (!dx_f32 && !dx_b16) ||
       !conv_shape(c, n, h, w, ci, co, ksize, stride))
     return (int)hipErrorInvalidValue;
   return (int)conv_dgrad_gated(c, static_cast<const bf16_t*>(dy_b16), static_cast<const bf16_t*>(wt_b16), addend_f32,
-                               static_cast<const bf16_t*>(gate_b16), static_cast<const bf16_t*>(bnx_b16), gsums_f32, dx_f32,
+                               static_cast<const bf16_t*>(gate_b16), static_cast<const bf16_t*>(bnx_b16), static_cast<stat_t*>(gsums), dx_f32,
                                static_cast<bf16_t*>(dx_b16), st(hip_stream));
 }
 
 int fdgk_conv_dgrad_feeding_next(const void* dy_b16, const void* wt_b16, const float* addend_f32, const void* addmask_b16,
-                                 const void* gate_b16, const void* bnx_b16, float* gsums_f32, float* dx_f32, void* dx_b16,
+                                 const void* gate_b16, const void* bnx_b16, void* gsums, float* dx_f32, void* dx_b16,
                                  int n, int h, int w, int ci, int co, int ksize, int stride, void* hip_stream) {
   ConvShape c;
-  if (!dy_b16 || !wt_b16 || !gate_b16 || !bnx_b16 || !gsums_f32 || !dx_f32 || !conv_shape(c, n, h, w, ci, co, ksize, stride))
+  if (!dy_b16 || !wt_b16 || !gate_b16 || !bnx_b16 || !gsums || !dx_f32 || !conv_shape(c, n, h, w, ci, co, ksize, stride))
     return (int)hipErrorInvalidValue;
   return (int)conv_dgrad_feeding_next(c, static_cast<const bf16_t*>(dy_b16), static_cast<const bf16_t*>(wt_b16), addend_f32,
                                       static_cast<const bf16_t*>(addmask_b16), static_cast<const bf16_t*>(gate_b16),
-                                      static_cast<const bf16_t*>(bnx_b16), gsums_f32, dx_f32, static_cast<bf16_t*>(dx_b16),
+                                      static_cast<const bf16_t*>(bnx_b16), static_cast<stat_t*>(gsums), dx_f32, static_cast<bf16_t*>(dx_b16),
                                       st(hip_stream));
 }
 
@@ -110,29 +112,47 @@ int fdgk_conv_wgrad(const void* x_b16, const void* dy_b16, float* dw_f32, float*
                          scratch_bytes, overwrite != 0, st(hip_stream));
 }
 
-int fdgk_bn_stats(const void* x_b16, float* sums_f32, int m, int c, void* hip_stream) {
-  if (!x_b16 || !sums_f32) return (int)hipErrorInvalidValue;
-  return (int)launch_bn_stats(static_cast<const bf16_t*>(x_b16), sums_f32, m, c, st(hip_stream));
+size_t fdgk_sums_bytes(int c) { return c > 0 ? stat_elems((size_t)c) * sizeof(stat_t) : 0; }
+
+int fdgk_sums_read(const void* sums, int c, double* host_out, void* hip_stream) {
+  if (!sums || !host_out || c <= 0) return (int)hipErrorInvalidValue;
+  hipError_t e = hipStreamSynchronize(st(hip_stream));
+  if (e != hipSuccess) return (int)e;
+  std::vector<stat_t> raw(stat_elems((size_t)c));
+  e = hipMemcpy(raw.data(), sums, raw.size() * sizeof(stat_t), hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return (int)e;
+  for (int i = 0; i < 2 * c; ++i) {   // words: hi [2][c], lo [2][c], big [2][c] (a double)
+    double big;
+    memcpy(&big, &raw[4 * (size_t)c + i], sizeof(big));
+    host_out[i] = big + ((double)raw[i] * 0x1p-11 + (double)raw[2 * (size_t)c + i] * 0x1p-62);
+  }
+  return 0;
 }
 
-int fdgk_bn_apply(const void* x_b16, const float* sums_f32, const float* gamma, const float* beta,
+int fdgk_bn_stats(const void* x_b16, void* sums, int m, int c, void* hip_stream) {
+  if (!x_b16 || !sums) return (int)hipErrorInvalidValue;
+  return (int)launch_bn_stats(static_cast<const bf16_t*>(x_b16), static_cast<stat_t*>(sums), m, c, st(hip_stream));
+}
+
+int fdgk_bn_apply(const void* x_b16, const void* sums, const float* gamma, const float* beta,
                   const float* res_f32, float* y_f32, void* y_b16, int m, int c, float eps, int relu,
                   void* hip_stream) {
-  if (!x_b16 || !sums_f32 || !gamma || !beta || (!y_f32 && !y_b16)) return (int)hipErrorInvalidValue;
+  if (!x_b16 || !sums || !gamma || !beta || (!y_f32 && !y_b16)) return (int)hipErrorInvalidValue;
   BnApplyArgs a{};
-  a.x = static_cast<const bf16_t*>(x_b16); a.sums = sums_f32; a.gamma = gamma; a.beta = beta; a.res_f32 = res_f32;
+  a.x = static_cast<const bf16_t*>(x_b16); a.sums = static_cast<const stat_t*>(sums); a.gamma = gamma; a.beta = beta; a.res_f32 = res_f32;
   a.out_f32 = y_f32; a.out_b16 = static_cast<bf16_t*>(y_b16);
   a.M = m; a.C = c; a.eps = eps; a.momentum = 0.f; a.relu = relu;
   return (int)launch_bn_apply(a, st(hip_stream));
 }
 
-int fdgk_bn_bwd(const void* dy, int dy_is_f32, const void* mask_b16, const void* x_b16, const float* sums_f32,
-                const float* gamma, float* scratch_f32, const float* addend_f32, float* dx_f32, void* dx_b16,
+int fdgk_bn_bwd(const void* dy, int dy_is_f32, const void* mask_b16, const void* x_b16, const void* sums,
+                const float* gamma, void* scratch_sums, const float* addend_f32, float* dx_f32, void* dx_b16,
                 float* dgamma, float* dbeta, int m, int c, float eps, void* hip_stream) {
-  if (!dy || !mask_b16 || !x_b16 || !sums_f32 || !gamma || !scratch_f32 || !dgamma || !dbeta) return (int)hipErrorInvalidValue;
+  if (!dy || !mask_b16 || !x_b16 || !sums || !gamma || !scratch_sums || !dgamma || !dbeta) return (int)hipErrorInvalidValue;
   BnBwdArgs a{};
   a.dy = dy; a.dy_is_f32 = dy_is_f32; a.mask = static_cast<const bf16_t*>(mask_b16);
-  a.x = static_cast<const bf16_t*>(x_b16); a.sums = sums_f32; a.gamma = gamma; a.bsums = scratch_f32;
+  a.x = static_cast<const bf16_t*>(x_b16); a.sums = static_cast<const stat_t*>(sums); a.gamma = gamma;
+  a.bsums = static_cast<stat_t*>(scratch_sums);
   a.addend = addend_f32; a.out_f32 = dx_f32; a.out_b16 = static_cast<bf16_t*>(dx_b16);
   a.dgamma = dgamma; a.dbeta = dbeta; a.M = m; a.C = c; a.eps = eps;
   hipError_t e = launch_bn_bwd_reduce(a, st(hip_stream));
@@ -142,29 +162,30 @@ int fdgk_bn_bwd(const void* dy, int dy_is_f32, const void* mask_b16, const void*
 
 int fdgk_bn_bwd_static_max_c(void) { return kStaticMaxC; }
 
-int fdgk_bn_bwd_static(const void* dy, int dy_is_f32, const void* mask_b16, const void* x_b16, const float* sums_f32,
+int fdgk_bn_bwd_static(const void* dy, int dy_is_f32, const void* mask_b16, const void* x_b16, const void* sums,
                        const float* gamma, const float* addend_f32, float* dx_f32, void* dx_b16, float* dgamma, float* dbeta,
                        int m, int c, float eps, void* hip_stream) {
-  if (!dy || !mask_b16 || !x_b16 || !sums_f32 || !gamma || !dgamma || !dbeta) return (int)hipErrorInvalidValue;
+  if (!dy || !mask_b16 || !x_b16 || !sums || !gamma || !dgamma || !dbeta) return (int)hipErrorInvalidValue;
   if (c <= 0 || c > kStaticMaxC || c % 8 != 0 || m <= 0) return (int)hipErrorInvalidValue;   // beyond the array: refused
   hipError_t e = hipSuccess;
-  float* sums2 = static_scratch(&e);
+  stat_t* sums2 = static_scratch(&e);
   if (!sums2) return (int)e;
   // the array keeps the last call's sums: the part this call adds into starts at zero (a fill kernel, so that a
   // caller may record the call into a graph)
-  e = launch_fill_zero(sums2, (size_t)2 * c * sizeof(float), st(hip_stream));
+  e = launch_fill_zero(sums2, stat_elems((size_t)c) * sizeof(stat_t), st(hip_stream));
   if (e != hipSuccess) return (int)e;
-  return fdgk_bn_bwd(dy, dy_is_f32, mask_b16, x_b16, sums_f32, gamma, sums2, addend_f32, dx_f32, dx_b16, dgamma, dbeta, m, c,
+  return fdgk_bn_bwd(dy, dy_is_f32, mask_b16, x_b16, sums, gamma, sums2, addend_f32, dx_f32, dx_b16, dgamma, dbeta, m, c,
                      eps, hip_stream);
 }
 
-int fdgk_bn_bwd_gated(const void* g_b16, const void* x_b16, const float* sums_f32, const float* gamma,
-                      const float* gsums_f32, const float* addend_f32, float* dx_f32, void* dx_b16, float* dgamma,
+int fdgk_bn_bwd_gated(const void* g_b16, const void* x_b16, const void* sums, const float* gamma,
+                      const void* gsums, const float* addend_f32, float* dx_f32, void* dx_b16, float* dgamma,
                       float* dbeta, int m, int c, float eps, void* hip_stream) {
-  if (!g_b16 || !x_b16 || !sums_f32 || !gamma || !gsums_f32 || !dgamma || !dbeta) return (int)hipErrorInvalidValue;
+  if (!g_b16 || !x_b16 || !sums || !gamma || !gsums || !dgamma || !dbeta) return (int)hipErrorInvalidValue;
   BnBwdArgs a{};
-  a.dy = g_b16; a.dy_is_f32 = 0; a.mask = nullptr; a.x = static_cast<const bf16_t*>(x_b16); a.sums = sums_f32;
-  a.gamma = gamma; a.bsums = const_cast<float*>(gsums_f32);
+  a.dy = g_b16; a.dy_is_f32 = 0; a.mask = nullptr; a.x = static_cast<const bf16_t*>(x_b16);
+  a.sums = static_cast<const stat_t*>(sums);
+  a.gamma = gamma; a.bsums = const_cast<stat_t*>(static_cast<const stat_t*>(gsums));
   a.addend = addend_f32; a.out_f32 = dx_f32; a.out_b16 = static_cast<bf16_t*>(dx_b16);
   a.dgamma = dgamma; a.dbeta = dbeta; a.M = m; a.C = c; a.eps = eps;
   a.dy_gated = 1; a.raw_sums = 1;

@@ -24,24 +24,77 @@ __device__ __forceinline__ void load8_f32(const float* p, float (&f)[8]) {
   const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
   f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
 }
-// the same, adding the copies of a replicated sums array (rep = floats between copies, 0: one copy)
-__device__ __forceinline__ void load8_rep(const float* p, int rep, float (&v)[8]) {
-  load8_f32(p, v);
-  if (rep > 0) {
+// ---- per-channel constants, worked out once per wave ------------------------------------------------
+// A thread of the elementwise kernels owns a group of 8 channels, and the 64 / CGB lanes of a wave that own the same
+// group would each repeat the 64-bit arithmetic that turns the group's exact totals into the constants of the row
+// loop.  Instead the lanes share it: lane (cgl = lane % CGB, sub = lane / CGB) takes channel sub % 8 of the group (two
+// channels, sub and sub + 4, when only four lanes share a group) and, where the sums exist in copies, the copies
+// sub / 8, sub / 8 + parts, ...; the integer words of the copies are added across those lanes, the lane works out the
+// constants of its channel(s), and they travel to the lanes that need them by lane shuffles.  No LDS.  Every lane of a
+// wave must take part (shuffles), also the lanes whose channel group does not exist.
+struct LaneShare {
+  int CGB, cgl, sub, nch, part, parts;
+  __device__ __forceinline__ explicit LaneShare(int cgb) : CGB(cgb) {
+    const int lane = threadIdx.x & 63, S = 64 / cgb;   // CGB divides 64
+    cgl = lane % cgb; sub = lane / cgb;
+    nch = S >= 8 ? 1 : 2;
+    part = S >= 8 ? sub / 8 : 0;
+    parts = S >= 8 ? S / 8 : 1;
+  }
+  // k-th channel of the group this lane works on (k < nch)
+  __device__ __forceinline__ int channel(int k) const { return nch == 1 ? sub % 8 : sub + 4 * k; }
+  // the value lane-computed for channel i of the group, given this lane's values r[k]
+  __device__ __forceinline__ float gather(const float (&r)[2], int i) const {
+    return nch == 1 ? __shfl(r[0], cgl + CGB * i) : __shfl(i < 4 ? r[0] : r[1], cgl + CGB * (i & 3));
+  }
+};
+// The words of one of the two sums (which = 0 / 1) of channel c in the COPIES copies this lane takes (copy part,
+// part + parts, ...; COPIES * parts = kStatReplicas, or COPIES = 1 and rep = 0 where the array is a single copy, which
+// every lane then reads).  Loads only -- nothing is added and nothing depends on `valid` (a lane without a channel is given
+// an existing one and its result is dropped) -- so that a kernel issues the loads of ALL the sums it needs back to back
+// and waits for memory once.
+template <int COPIES>
+struct RawTotal { long long hi[COPIES], lo[COPIES], big[COPIES]; };
+template <int COPIES>
+__device__ __forceinline__ void chan_load(RawTotal<COPIES>& t, const LaneShare& ls, const stat_t* stats, int C, int which, int c, int rep) {
+  const stat_t* p = stats + (size_t)which * C + c;
 #pragma unroll
-    for (int r = 1; r < kStatReplicas; ++r) {
-      float t[8];
-      load8_f32(p + (size_t)r * rep, t);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) v[i] += t[i];
-    }
+  for (int j = 0; j < COPIES; ++j) {
+    const stat_t* q = p + (size_t)(ls.part + j * ls.parts) * rep;
+    t.hi[j] = q[0];
+    t.lo[j] = q[2 * (size_t)C];
+    t.big[j] = q[4 * (size_t)C];
   }
 }
-__device__ __forceinline__ float load_rep(const float* p, int rep) {
-  float v = p[0];
+// The total: this lane's copies (added as integers, hence independent of the order the workgroups arrived in) as a
+// double, then -- where there are copies -- the other lanes' in a fixed order.
+template <int COPIES>
+__device__ __forceinline__ double chan_total(const RawTotal<COPIES>& t, const LaneShare& ls, int rep) {
+  long long hi = 0, lo = 0;
+  double big = 0.0;
+#pragma unroll
+  for (int j = 0; j < COPIES; ++j) {
+    hi += t.hi[j];
+    lo += t.lo[j];
+    big += __builtin_bit_cast(double, t.big[j]);
+  }
+  double v = stat_value(hi, lo, __builtin_bit_cast(long long, big));
   if (rep > 0)
-    for (int r = 1; r < kStatReplicas; ++r) v += p[(size_t)r * rep];
+    for (int off = 8 * ls.CGB; off < 64; off <<= 1) v += __shfl_xor(v, off);   // lanes 8 * CGB apart hold the other copies
   return v;
+}
+// copies a lane takes for an array with (rep > 0) or without copies: the template argument of the functions above
+static int host_copies_per_lane(int CGB, int rep) {
+  const int S = 64 / CGB, parts = S >= 8 ? S / 8 : 1;   // as in LaneShare
+  return rep > 0 ? kStatReplicas / parts : 1;
+}
+// Batch mean and 1 / sqrt(variance + eps) from the totals sum x and sum x^2 over M rows.  The subtraction that gives the
+// variance is done in double on the exact totals, so a mean that is large against the spread costs no digits here.
+__device__ __forceinline__ void bn_moments(double s1, double s2, double invM, float eps, float& mean, float& is) {
+  const double m = s1 * invM;
+  const double var = fmax(s2 * invM - m * m, 0.0);
+  mean = (float)m;
+  is = rsqrtf((float)var + eps);
 }
 __device__ __forceinline__ void store8_f32(float* p, const float (&f)[8]) {
   *reinterpret_cast<float4*>(p) = make_float4(f[0], f[1], f[2], f[3]);
@@ -76,7 +129,7 @@ static ReduceShape reduce_shape(int M, int C) {
 }
 
 template <int NV>
-__device__ __forceinline__ void block_reduce_to_global(float (&v)[NV][8], float* const (&dst)[NV], int cgl, int rl, int CGB,
+__device__ __forceinline__ void block_reduce_to_global(float (&v)[NV][8], stat_t* stats, int cgl, int rl, int CGB,
                                                        int RL, int c_base, int C, float* smem /* [NV][RL][CGB*8] */) {
   const int W = CGB * 8;
 #pragma unroll
@@ -89,12 +142,12 @@ __device__ __forceinline__ void block_reduce_to_global(float (&v)[NV][8], float*
     if (c_base + col >= C) continue;
     float s = 0.f;
     for (int rr = 0; rr < RL; ++rr) s += smem[(q * RL + rr) * W + col];
-    atomicAdd(dst[q] + c_base + col, s);
+    stat_add(stats, C, q, c_base + col, s);
   }
 }
 
 // ---- BN forward statistics: sums[c] += sum x, sums[C + c] += sum x^2 --------------------------------
-__global__ __launch_bounds__(kThreads) void bn_stats_kernel(const bf16_t* __restrict__ x, float* __restrict__ sums, int M,
+__global__ __launch_bounds__(kThreads) void bn_stats_kernel(const bf16_t* __restrict__ x, stat_t* __restrict__ sums, int M,
                                                             int C, int CGB, int rows_per_block) {
   extern __shared__ float smem[];
   const int RL = kThreads / CGB;
@@ -117,11 +170,10 @@ __global__ __launch_bounds__(kThreads) void bn_stats_kernel(const bf16_t* __rest
       }
     }
   }
-  float* const dst[2] = {sums, sums + C};
-  block_reduce_to_global<2>(v, dst, cgl, rl, CGB, RL, blockIdx.x * CGB * 8, C, smem);
+  block_reduce_to_global<2>(v, sums, cgl, rl, CGB, RL, blockIdx.x * CGB * 8, C, smem);
 }
 
-hipError_t launch_bn_stats(const bf16_t* x, float* sums, int M, int C, hipStream_t s) {
+hipError_t launch_bn_stats(const bf16_t* x, stat_t* sums, int M, int C, hipStream_t s) {
   if (C % 8 != 0 || C > 2048 || M <= 0) return hipErrorInvalidValue;
   const ReduceShape r = reduce_shape(M, C);
   hipLaunchKernelGGL(bn_stats_kernel, r.grid, dim3(kThreads), 2 * kThreads * 8 * sizeof(float), s, x, sums, M, C, r.CGB,
@@ -130,13 +182,13 @@ hipError_t launch_bn_stats(const bf16_t* x, float* sums, int M, int C, hipStream
 }
 
 // ---- BN apply: y = relu?( gamma*xhat + beta [+ res] [+ gamma2*xhat2 + beta2] ) ------------------------
-__device__ __forceinline__ void bn_running(const float* sums, int rep, float* run_mean, float* run_var, int C, int M, float mom) {
-  const float invM = 1.f / (float)M;
+__device__ __forceinline__ void bn_running(const stat_t* sums, int rep, float* run_mean, float* run_var, int C, int M, float mom) {
+  const double invM = 1.0 / (double)M;
   const float unbias = M > 1 ? (float)M / (float)(M - 1) : 1.f;
   for (int c = threadIdx.x; c < C; c += blockDim.x) {
-    const float mean = load_rep(sums + c, rep) * invM;
-    const float var = fmaxf(load_rep(sums + C + c, rep) * invM - mean * mean, 0.f);
-    run_mean[c] = (1.f - mom) * run_mean[c] + mom * mean;
+    const double mean = stat_load(sums, C, 0, c, rep) * invM;
+    const float var = (float)fmax(stat_load(sums, C, 1, c, rep) * invM - mean * mean, 0.0);
+    run_mean[c] = (1.f - mom) * run_mean[c] + mom * (float)mean;
     run_var[c] = (1.f - mom) * run_var[c] + mom * var * unbias;
   }
 }
@@ -151,10 +203,13 @@ struct ApplyShape {
 static ApplyShape apply_shape(int M, int C) {
   ApplyShape r;
   const int CG = C / 8;
-  r.CGB = CG >= 16 ? 16 : (CG >= 8 ? 8 : (CG >= 4 ? 4 : (CG >= 2 ? 2 : 1)));
+  // at most 8 groups (64 channels) per block: eight lanes of a wave then share a group and each works out the constants
+  // of ONE channel (LaneShare); with 16 groups a lane has two channels and the kernels of the 640-channel layers lose
+  // 2 - 3 us per launch
+  r.CGB = CG >= 8 ? 8 : (CG >= 4 ? 4 : (CG >= 2 ? 2 : 1));
   r.RL = kThreads / r.CGB;
   const int cblocks = (CG + r.CGB - 1) / r.CGB;
-  int rblocks = (2048 + cblocks - 1) / cblocks;
+  int rblocks = (1024 + cblocks - 1) / cblocks;                 // four workgroups per compute unit: one round of waves
   const int max_rblocks = (M + r.RL * 4 - 1) / (r.RL * 4);      // at least four rows per thread
   if (rblocks > max_rblocks) rblocks = max_rblocks;
   if (rblocks < 1) rblocks = 1;
@@ -165,84 +220,66 @@ static ApplyShape apply_shape(int M, int C) {
   return r;
 }
 
-// The copies of NA replicated per-channel arrays added once per block instead of once per thread: thread
-// (cgl = tid % CGB, rl = tid / CGB) with rl < kStatReplicas loads copy rl of its channel group (8 floats per array),
-// the copies are added across the lanes of wave 0 (needs kStatReplicas * CGB <= 64, CGB a power of two) and parked
-// in LDS, where every thread of the block picks up the sums of its channel group.  All threads of the block call.
-template <int NA>
-__device__ __forceinline__ void fold_replicas(const float* const (&src)[NA], const int (&rep)[NA], int c0, bool cvalid, int CGB,
-                                              float (&out)[NA][8]) {
-  __shared__ float4 parked[8][NA][2];
-  const int cgl = threadIdx.x % CGB, rl = threadIdx.x / CGB;
-  if (rl < kStatReplicas) {
-    float v[NA][8];
-#pragma unroll
-    for (int a = 0; a < NA; ++a) {
-      if (cvalid && (rl == 0 || rep[a] > 0)) load8_f32(src[a] + c0 + (size_t)rl * rep[a], v[a]);
-      else {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) v[a][i] = 0.f;
-      }
+// scale and shift of the 8 channels from c0 on (and of the second operand's, if there is one), see LaneShare
+template <int COPIES>
+__device__ __forceinline__ void bn_apply_setup(const BnApplyArgs& a, const LaneShare& ls, int c0, float (&sc)[8], float (&sh)[8],
+                                               float (&sc2)[8], float (&sh2)[8]) {
+  const int C = a.C;
+  const double invM = 1.0 / (double)a.M;
+  const bool two = a.x2 != nullptr;
+  const stat_t* sums2 = two ? a.sums2 : a.sums;
+  const float *gamma2 = two ? a.gamma2 : a.gamma, *beta2 = two ? a.beta2 : a.beta;
+  RawTotal<COPIES> raw[2][2][2];   // [channel of this lane][x | x2][sum | sum of squares]
+  float gm[2][2], bt[2][2];
+  float r_sc[2] = {0.f, 0.f}, r_sh[2] = {0.f, 0.f}, r_sc2[2] = {0.f, 0.f}, r_sh2[2] = {0.f, 0.f};
+  auto load = [&](int k) {   // called with constants: the arrays stay in registers
+    const int c = c0 + ls.channel(k);
+    chan_load(raw[k][0][0], ls, a.sums, C, 0, c, a.rep_stride);
+    chan_load(raw[k][0][1], ls, a.sums, C, 1, c, a.rep_stride);
+    gm[k][0] = a.gamma[c];
+    bt[k][0] = a.beta[c];
+    if (two) {
+      chan_load(raw[k][1][0], ls, sums2, C, 0, c, a.rep_stride);
+      chan_load(raw[k][1][1], ls, sums2, C, 1, c, a.rep_stride);
+      gm[k][1] = gamma2[c];
+      bt[k][1] = beta2[c];
     }
-    for (int off = CGB; off < kStatReplicas * CGB; off <<= 1) {
-#pragma unroll
-      for (int a = 0; a < NA; ++a)
-#pragma unroll
-        for (int i = 0; i < 8; ++i) v[a][i] += __shfl_xor(v[a][i], off);
+  };
+  auto compute = [&](int k) {
+    float mean, is;
+    bn_moments(chan_total(raw[k][0][0], ls, a.rep_stride), chan_total(raw[k][0][1], ls, a.rep_stride), invM, a.eps, mean, is);
+    r_sc[k] = gm[k][0] * is;
+    r_sh[k] = bt[k][0] - mean * r_sc[k];
+    if (two) {
+      bn_moments(chan_total(raw[k][1][0], ls, a.rep_stride), chan_total(raw[k][1][1], ls, a.rep_stride), invM, a.eps, mean, is);
+      r_sc2[k] = gm[k][1] * is;
+      r_sh2[k] = bt[k][1] - mean * r_sc2[k];
     }
-    if (rl == 0) {
-#pragma unroll
-      for (int a = 0; a < NA; ++a) {
-        parked[cgl][a][0] = make_float4(v[a][0], v[a][1], v[a][2], v[a][3]);
-        parked[cgl][a][1] = make_float4(v[a][4], v[a][5], v[a][6], v[a][7]);
-      }
-    }
+  };
+  // every load first (one wait for memory), then the arithmetic -- unless a lane has two channels in eight copies each,
+  // which would not fit the registers
+  load(0);
+  if (COPIES < 8 && ls.nch == 2) load(1);
+  compute(0);
+  if (ls.nch == 2) {
+    if (COPIES >= 8) load(1);
+    compute(1);
   }
-  __syncthreads();
-#pragma unroll
-  for (int a = 0; a < NA; ++a) {
-    const float4 lo = parked[cgl][a][0], hi = parked[cgl][a][1];
-    out[a][0] = lo.x; out[a][1] = lo.y; out[a][2] = lo.z; out[a][3] = lo.w;
-    out[a][4] = hi.x; out[a][5] = hi.y; out[a][6] = hi.z; out[a][7] = hi.w;
-  }
-}
-
-// scale / shift of 8 channels from the accumulated sums
-__device__ __forceinline__ void bn_coeffs8(const float* sums, int rep, const float* gamma, const float* beta, int C, int c0, float invM,
-                                           float eps, float (&sc)[8], float (&sh)[8]) {
-  float s1[8], s2[8], g[8], b[8];
-  load8_rep(sums + c0, rep, s1);
-  load8_rep(sums + C + c0, rep, s2);
-  load8_f32(gamma + c0, g);
-  load8_f32(beta + c0, b);
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const float mean = s1[i] * invM;
-    const float var = fmaxf(s2[i] * invM - mean * mean, 0.f);
-    const float gi = g[i] * rsqrtf(var + eps);
-    sc[i] = gi;
-    sh[i] = b[i] - mean * gi;
+    sc[i] = ls.gather(r_sc, i);
+    sh[i] = ls.gather(r_sh, i);
   }
-}
-
-__device__ __forceinline__ void bn_coeffs8_from(const float (&s1)[8], const float (&s2)[8], const float* gamma, const float* beta,
-                                                int c0, float invM, float eps, float (&sc)[8], float (&sh)[8]) {
-  float g[8], b[8];
-  load8_f32(gamma + c0, g);
-  load8_f32(beta + c0, b);
+  if (two) {
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const float mean = s1[i] * invM;
-    const float var = fmaxf(s2[i] * invM - mean * mean, 0.f);
-    const float gi = g[i] * rsqrtf(var + eps);
-    sc[i] = gi;
-    sh[i] = b[i] - mean * gi;
+    for (int i = 0; i < 8; ++i) {
+      sc2[i] = ls.gather(r_sc2, i);
+      sh2[i] = ls.gather(r_sh2, i);
+    }
   }
 }
 
-// FOLD: the sums are replicated and added once per block through LDS; a kernel of its own so that the plain form
-// allocates no LDS (it then fits beside workgroups of the convolutions that fill a compute unit's LDS).
-template <bool FOLD>
+template <int COPIES>   // copies of the sums a lane takes (copies_per_lane): a kernel each, so that each has the registers it needs
 __global__ __launch_bounds__(kThreads) void bn_apply_kernel(BnApplyArgs a, int CGB, int rows_per_block) {
   const int C = a.C;
   if (blockIdx.x == 0 && blockIdx.y == 0) {
@@ -252,27 +289,27 @@ __global__ __launch_bounds__(kThreads) void bn_apply_kernel(BnApplyArgs a, int C
   const int RL = kThreads / CGB;
   const int cg = blockIdx.x * CGB + threadIdx.x % CGB, rl = threadIdx.x / CGB;
   const int c0 = cg * 8;
-  const float invM = 1.f / (float)a.M;
-  float sc[8], sh[8], sc2[8], sh2[8];
-  if constexpr (FOLD) {
-    const float* const src[4] = {a.sums, a.sums + C, a.x2 ? a.sums2 : a.sums, a.x2 ? a.sums2 + C : a.sums + C};
-    const int rep[4] = {a.rep_stride, a.rep_stride, a.rep_stride, a.rep_stride};
-    float f[4][8];
-    fold_replicas<4>(src, rep, c0, c0 < C, CGB, f);
-    if (c0 >= C) return;
-    bn_coeffs8_from(f[0], f[1], a.gamma, a.beta, c0, invM, a.eps, sc, sh);
-    if (a.x2) bn_coeffs8_from(f[2], f[3], a.gamma2, a.beta2, c0, invM, a.eps, sc2, sh2);
-  } else {
-    if (c0 >= C) return;
-    bn_coeffs8(a.sums, a.rep_stride, a.gamma, a.beta, C, c0, invM, a.eps, sc, sh);
-    if (a.x2) bn_coeffs8(a.sums2, a.rep_stride, a.gamma2, a.beta2, C, c0, invM, a.eps, sc2, sh2);
-  }
+  // The first rows of this thread are requested BEFORE the per-channel constants are worked out, so that the two trips
+  // to memory overlap (a launch of this kernel lasts about as long as two trips take).
+  constexpr int NPRE = 4;
   const int row_lo = blockIdx.y * rows_per_block, row_hi = min(a.M, row_lo + rows_per_block);
-#pragma unroll 4
-  for (int row = row_lo + rl; row < row_hi; row += RL) {
+  uint4 px[NPRE];
+#pragma unroll
+  for (int j = 0; j < NPRE; ++j) {
+    const int row = row_lo + rl + j * RL;
+    px[j] = (c0 < C && row < row_hi) ? *reinterpret_cast<const uint4*>(a.x + (size_t)row * C + c0) : make_uint4(0u, 0u, 0u, 0u);
+  }
+  float sc[8], sh[8], sc2[8], sh2[8];
+  {
+    const LaneShare ls(CGB);
+    const bool valid = c0 < C;
+    bn_apply_setup<COPIES>(a, ls, valid ? c0 : 0, sc, sh, sc2, sh2);
+    if (!valid) return;
+  }
+  auto one_row = [&](int row, const uint4& xu) {
     const size_t o = (size_t)row * C + c0;
     float f[8];
-    unpack8(*reinterpret_cast<const uint4*>(a.x + o), f);
+    unpack8(xu, f);
 #pragma unroll
     for (int i = 0; i < 8; ++i) f[i] = f[i] * sc[i] + sh[i];
     if (a.res_f32) {
@@ -293,7 +330,14 @@ __global__ __launch_bounds__(kThreads) void bn_apply_kernel(BnApplyArgs a, int C
     }
     if (a.out_f32) store8_f32(a.out_f32 + o, f);
     if (a.out_b16) *reinterpret_cast<uint4*>(a.out_b16 + o) = pack8(f);
+  };
+#pragma unroll
+  for (int j = 0; j < NPRE; ++j) {
+    const int row = row_lo + rl + j * RL;
+    if (row < row_hi) one_row(row, px[j]);
   }
+#pragma unroll 4
+  for (int row = row_lo + rl + NPRE * RL; row < row_hi; row += RL) one_row(row, *reinterpret_cast<const uint4*>(a.x + (size_t)row * C + c0));
 }
 
 static int stream_grid(size_t units) {
@@ -309,10 +353,12 @@ hipError_t launch_bn_apply(const BnApplyArgs& a, hipStream_t s) {
   if (!al16(a.sums) || !al16(a.gamma) || !al16(a.beta) || (a.x2 && (!al16(a.sums2) || !al16(a.gamma2) || !al16(a.beta2))))
     return hipErrorInvalidValue;   // per-channel vectors are read 16 bytes at a time
   const ApplyShape r = apply_shape(a.M, a.C);
-  if (a.rep_stride > 0 && r.CGB * kStatReplicas <= 64)
-    hipLaunchKernelGGL(bn_apply_kernel<true>, r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block);
-  else
-    hipLaunchKernelGGL(bn_apply_kernel<false>, r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block);
+  switch (host_copies_per_lane(r.CGB, a.rep_stride)) {
+    case 1: hipLaunchKernelGGL(bn_apply_kernel<1>, r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block); break;
+    case 2: hipLaunchKernelGGL(bn_apply_kernel<2>, r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block); break;
+    case 4: hipLaunchKernelGGL(bn_apply_kernel<4>, r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block); break;
+    default: hipLaunchKernelGGL(bn_apply_kernel<8>, r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block); break;
+  }
   return hipGetLastError();
 }
 
@@ -331,7 +377,31 @@ __device__ __forceinline__ void load_masked_dy(const void* dy, const bf16_t* mas
     if (!(mk[i] > 0.f)) g[i] = 0.f;
 }
 
-template <bool DY_F32>
+// batch mean and 1 / sqrt(variance + eps) of the 8 channels from c0 on, see LaneShare
+template <int COPIES>
+__device__ __forceinline__ void bn_moments_setup(const stat_t* sums, int rep, int C, int M, float eps, const LaneShare& ls, int c0,
+                                                 float (&mu)[8], float (&iv)[8]) {
+  const double invM = 1.0 / (double)M;
+  RawTotal<COPIES> raw[2][2];
+  float r_mu[2] = {0.f, 0.f}, r_iv[2] = {0.f, 0.f};
+  auto load = [&](int k) {   // called with constants: the arrays stay in registers
+    const int c = c0 + ls.channel(k);
+    chan_load(raw[k][0], ls, sums, C, 0, c, rep);
+    chan_load(raw[k][1], ls, sums, C, 1, c, rep);
+  };
+  auto compute = [&](int k) { bn_moments(chan_total(raw[k][0], ls, rep), chan_total(raw[k][1], ls, rep), invM, eps, r_mu[k], r_iv[k]); };
+  load(0);
+  if (ls.nch == 2) load(1);
+  compute(0);
+  if (ls.nch == 2) compute(1);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    mu[i] = ls.gather(r_mu, i);
+    iv[i] = ls.gather(r_iv, i);
+  }
+}
+
+template <bool DY_F32, int COPIES>
 __global__ __launch_bounds__(kThreads) void bn_bwd_reduce_kernel(BnBwdArgs a, int CGB, int rows_per_block) {
   extern __shared__ float smem[];  // 2 * 256 * 8 floats
   const int C = a.C;
@@ -343,16 +413,12 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_reduce_kernel(BnBwdArgs a, in
   float v[2][8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) v[0][i] = v[1][i] = 0.f;
+  {
+    const LaneShare ls(CGB);
+    const int c0 = cvalid ? cg * 8 : 0;
+    bn_moments_setup<COPIES>(a.sums, a.rep_stride, C, a.M, a.eps, ls, c0, mu, iv);
+  }
   if (cvalid) {
-    const float invM = 1.f / (float)a.M;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int c = cg * 8 + i;
-      const float m = load_rep(a.sums + c, a.rep_stride) * invM;
-      const float var = fmaxf(load_rep(a.sums + C + c, a.rep_stride) * invM - m * m, 0.f);
-      mu[i] = m;
-      iv[i] = rsqrtf(var + a.eps);
-    }
     const int row_lo = blockIdx.y * rows_per_block, row_hi = min(a.M, row_lo + rows_per_block);
 #pragma unroll 2
     for (int row = row_lo + rl; row < row_hi; row += RL) {
@@ -367,73 +433,120 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_reduce_kernel(BnBwdArgs a, in
       }
     }
   }
-  float* const dst[2] = {a.bsums, a.bsums + C};
-  block_reduce_to_global<2>(v, dst, cgl, rl, CGB, RL, blockIdx.x * CGB * 8, C, smem);
+  block_reduce_to_global<2>(v, a.bsums, cgl, rl, CGB, RL, blockIdx.x * CGB * 8, C, smem);
 }
 
 hipError_t launch_bn_bwd_reduce(const BnBwdArgs& a, hipStream_t s) {
   if (a.C % 8 != 0 || a.C > 2048 || a.M <= 0 || !a.mask) return hipErrorInvalidValue;
   const ReduceShape r = reduce_shape(a.M, a.C);
   const size_t sm = 2 * (size_t)kThreads * 8 * sizeof(float);
-  if (a.dy_is_f32)
-    hipLaunchKernelGGL(bn_bwd_reduce_kernel<true>, r.grid, dim3(kThreads), sm, s, a, r.CGB, r.rows_per_block);
-  else
-    hipLaunchKernelGGL(bn_bwd_reduce_kernel<false>, r.grid, dim3(kThreads), sm, s, a, r.CGB, r.rows_per_block);
+#define FDG_LAUNCH_REDUCE(F32, CP) \
+  hipLaunchKernelGGL((bn_bwd_reduce_kernel<F32, CP>), r.grid, dim3(kThreads), sm, s, a, r.CGB, r.rows_per_block)
+  switch (host_copies_per_lane(r.CGB, a.rep_stride)) {
+    case 1: if (a.dy_is_f32) FDG_LAUNCH_REDUCE(true, 1); else FDG_LAUNCH_REDUCE(false, 1); break;
+    case 2: if (a.dy_is_f32) FDG_LAUNCH_REDUCE(true, 2); else FDG_LAUNCH_REDUCE(false, 2); break;
+    case 4: if (a.dy_is_f32) FDG_LAUNCH_REDUCE(true, 4); else FDG_LAUNCH_REDUCE(false, 4); break;
+    default: if (a.dy_is_f32) FDG_LAUNCH_REDUCE(true, 8); else FDG_LAUNCH_REDUCE(false, 8); break;
+  }
+#undef FDG_LAUNCH_REDUCE
   return hipGetLastError();
 }
 
+// Constants of the batch-norm backward for the 8 channels from c0 on, see LaneShare.  Per channel: xhat = x*is - mean*is;
+// dx = gi*g - gi*k1 - gi*k2*xhat = gi*g + (pa*x + pb).  The lanes with `writes` store dbeta and dgamma of their channel(s).
+// The forward and the backward sums have copies (a.rep_stride == a.brep_stride > 0) or neither has.
+template <int COPIES>
+__device__ __forceinline__ void bn_bwd_setup(const BnBwdArgs& a, const LaneShare& ls, int c0, bool writes, float (&gi)[8],
+                                             float (&pa)[8], float (&pb)[8]) {
+  const int C = a.C, rep = a.rep_stride;
+  const double invMd = 1.0 / (double)a.M;
+  const float invM = (float)invMd;
+  RawTotal<COPIES> raw[2][2][2];   // [channel of this lane][forward sums | backward sums][first | second sum]
+  float gm[2];
+  float r_gi[2] = {0.f, 0.f}, r_pa[2] = {0.f, 0.f}, r_pb[2] = {0.f, 0.f};
+  auto load = [&](int k) {   // called with constants: the arrays stay in registers
+    const int c = c0 + ls.channel(k);
+    chan_load(raw[k][0][0], ls, a.sums, C, 0, c, rep);
+    chan_load(raw[k][0][1], ls, a.sums, C, 1, c, rep);
+    chan_load(raw[k][1][0], ls, a.bsums, C, 0, c, rep);
+    chan_load(raw[k][1][1], ls, a.bsums, C, 1, c, rep);
+    gm[k] = a.gamma[c];
+  };
+  auto compute = [&](int k) {
+    const int c = c0 + ls.channel(k);
+    const double s1 = chan_total(raw[k][0][0], ls, rep), s2 = chan_total(raw[k][0][1], ls, rep);
+    const double t1 = chan_total(raw[k][1][0], ls, rep), t2 = chan_total(raw[k][1][1], ls, rep);
+    float mean, is;
+    bn_moments(s1, s2, invMd, a.eps, mean, is);
+    const float b1 = (float)t1;
+    // sum g*xhat from sum g*x and sum g: the difference is taken in double on the exact totals
+    const float b2 = a.raw_sums ? is * (float)(t2 - (s1 * invMd) * t1) : (float)t2;
+    const float g = gm[k] * is;
+    const float k1 = b1 * invM, k2 = b2 * invM;
+    r_gi[k] = g;
+    r_pa[k] = -g * k2 * is;
+    r_pb[k] = -g * k1 + g * k2 * is * mean;
+    if (writes) {
+      a.dbeta[c] = b1;
+      a.dgamma[c] = b2;
+    }
+  };
+  // every load first (one wait for memory), then the arithmetic -- unless a lane has two channels in eight copies each,
+  // which would not fit the registers
+  load(0);
+  if (COPIES < 8 && ls.nch == 2) load(1);
+  compute(0);
+  if (ls.nch == 2) {
+    if (COPIES >= 8) load(1);
+    compute(1);
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    gi[i] = ls.gather(r_gi, i);
+    pa[i] = ls.gather(r_pa, i);
+    pb[i] = ls.gather(r_pb, i);
+  }
+}
+
 // dx = gamma*invstd*(g - S1/M - xhat*S2/M) [+ addend];  dgamma = S2, dbeta = S1
-template <bool DY_F32, bool FOLD>
+template <bool DY_F32, int COPIES>
 __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(BnBwdArgs a, int CGB, int rows_per_block) {
   const int C = a.C;
   const int RL = kThreads / CGB;
   const int cg = blockIdx.x * CGB + threadIdx.x % CGB, rl = threadIdx.x / CGB;
   const int c0 = cg * 8;
-  const float invM = 1.f / (float)a.M;
-  // per channel: xhat = x*is - mean*is;  dx = gi*g - gi*k1 - gi*k2*xhat = gi*g + (pa*x + pb)
+  // as in bn_apply_kernel: the first rows are requested before the per-channel constants are worked out
+  constexpr int NPRE = 4;
+  const bool rows_wanted = a.out_f32 || a.out_b16;
+  const int row_lo = blockIdx.y * rows_per_block, row_hi = rows_wanted ? min(a.M, row_lo + rows_per_block) : 0;
+  uint4 pdy[NPRE][DY_F32 ? 2 : 1], px[NPRE], pmk[NPRE];
+#pragma unroll
+  for (int j = 0; j < NPRE; ++j) {
+    const int row = row_lo + rl + j * RL;
+    const bool on = c0 < C && row < row_hi;
+    const size_t o = on ? (size_t)row * C + c0 : 0;
+    if (DY_F32) {
+      pdy[j][0] = on ? *reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(a.dy) + o) : make_uint4(0u, 0u, 0u, 0u);
+      pdy[j][DY_F32 ? 1 : 0] = on ? *reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(a.dy) + o + 4) : make_uint4(0u, 0u, 0u, 0u);
+    } else {
+      pdy[j][0] = on ? *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(a.dy) + o) : make_uint4(0u, 0u, 0u, 0u);
+    }
+    px[j] = on ? *reinterpret_cast<const uint4*>(a.x + o) : make_uint4(0u, 0u, 0u, 0u);
+    pmk[j] = (on && a.mask) ? *reinterpret_cast<const uint4*>(a.mask + o) : make_uint4(0u, 0u, 0u, 0u);
+  }
   float gi[8], pa[8], pb[8];
   {
-    float s1[8], s2[8], gm[8], b1[8], b2[8];
-    if constexpr (FOLD) {   // replicated sums: added once per block through LDS (see bn_apply_kernel)
-      const float* const src[4] = {a.sums, a.sums + C, a.bsums, a.bsums + C};
-      const int rep[4] = {a.rep_stride, a.rep_stride, a.brep_stride, a.brep_stride};
-      float f[4][8];
-      fold_replicas<4>(src, rep, c0, c0 < C, CGB, f);
-      if (c0 >= C) return;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) { s1[i] = f[0][i]; s2[i] = f[1][i]; b1[i] = f[2][i]; b2[i] = f[3][i]; }
-    } else {
-      if (c0 >= C) return;
-      load8_rep(a.sums + c0, a.rep_stride, s1);
-      load8_rep(a.sums + C + c0, a.rep_stride, s2);
-      load8_rep(a.bsums + c0, a.brep_stride, b1);
-      load8_rep(a.bsums + C + c0, a.brep_stride, b2);
-    }
-    load8_f32(a.gamma + c0, gm);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const float mean = s1[i] * invM;
-      const float var = fmaxf(s2[i] * invM - mean * mean, 0.f);
-      const float is = rsqrtf(var + a.eps);
-      if (a.raw_sums) b2[i] = is * (b2[i] - mean * b1[i]);   // sum g*xhat from sum g*x and sum g
-      gi[i] = gm[i] * is;
-      const float k1 = b1[i] * invM, k2 = b2[i] * invM;
-      pa[i] = -gi[i] * k2 * is;
-      pb[i] = -gi[i] * k1 + gi[i] * k2 * is * mean;
-    }
-    if (blockIdx.y == 0 && rl == 0) {
-      store8_f32(a.dbeta + c0, b1);
-      store8_f32(a.dgamma + c0, b2);
-    }
+    const LaneShare ls(CGB);
+    const bool valid = c0 < C;
+    const bool writes = valid && blockIdx.y == 0 && threadIdx.x < 64 && ls.part == 0;   // one lane per channel of the block
+    bn_bwd_setup<COPIES>(a, ls, valid ? c0 : 0, writes, gi, pa, pb);
+    if (!valid) return;
   }
-  if (!a.out_f32 && !a.out_b16) return;
-  const int row_lo = blockIdx.y * rows_per_block, row_hi = min(a.M, row_lo + rows_per_block);
-#pragma unroll 4
-  for (int row = row_lo + rl; row < row_hi; row += RL) {
+  if (!rows_wanted) return;
+  auto finish_row = [&](int row, float (&g)[8], const uint4& xu) {
     const size_t o = (size_t)row * C + c0;
-    float g[8], xv[8];
-    load_masked_dy<DY_F32>(a.dy, a.mask, o, g);
-    unpack8(*reinterpret_cast<const uint4*>(a.x + o), xv);
+    float xv[8];
+    unpack8(xu, xv);
 #pragma unroll
     for (int i = 0; i < 8; ++i) g[i] = gi[i] * g[i] + (pa[i] * xv[i] + pb[i]);
     if (a.addend) {
@@ -444,6 +557,35 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(BnBwdArgs a, int
     }
     if (a.out_f32) store8_f32(a.out_f32 + o, g);
     if (a.out_b16) *reinterpret_cast<uint4*>(a.out_b16 + o) = pack8(g);
+  };
+#pragma unroll
+  for (int j = 0; j < NPRE; ++j) {
+    const int row = row_lo + rl + j * RL;
+    if (row >= row_hi) continue;
+    float g[8];
+    if (DY_F32) {
+      const uint4 lo = pdy[j][0], hi = pdy[j][DY_F32 ? 1 : 0];
+      g[0] = __builtin_bit_cast(float, lo.x); g[1] = __builtin_bit_cast(float, lo.y); g[2] = __builtin_bit_cast(float, lo.z);
+      g[3] = __builtin_bit_cast(float, lo.w); g[4] = __builtin_bit_cast(float, hi.x); g[5] = __builtin_bit_cast(float, hi.y);
+      g[6] = __builtin_bit_cast(float, hi.z); g[7] = __builtin_bit_cast(float, hi.w);
+    } else {
+      unpack8(pdy[j][0], g);
+    }
+    if (a.mask) {
+      float mk[8];
+      unpack8(pmk[j], mk);
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (!(mk[i] > 0.f)) g[i] = 0.f;
+    }
+    finish_row(row, g, px[j]);
+  }
+#pragma unroll 4
+  for (int row = row_lo + rl + NPRE * RL; row < row_hi; row += RL) {
+    const size_t o = (size_t)row * C + c0;
+    float g[8];
+    load_masked_dy<DY_F32>(a.dy, a.mask, o, g);
+    finish_row(row, g, *reinterpret_cast<const uint4*>(a.x + o));
   }
 }
 
@@ -453,16 +595,18 @@ hipError_t launch_bn_bwd_apply(const BnBwdArgs& a_in, hipStream_t s) {
   if (a.C % 8 != 0 || a.C > 2048 || a.M <= 0 || (!a.mask && !a.dy_gated)) return hipErrorInvalidValue;
   const auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
   if (!al16(a.sums) || !al16(a.gamma) || !al16(a.bsums) || !al16(a.dgamma) || !al16(a.dbeta)) return hipErrorInvalidValue;
+  if (a.rep_stride != a.brep_stride) return hipErrorInvalidValue;   // copies of both sums arrays, or of neither
   ApplyShape r = apply_shape(a.M, a.C);
   if (!a.out_f32 && !a.out_b16) r.grid.y = 1;   // only dgamma / dbeta
-  const bool fold = (a.rep_stride > 0 || a.brep_stride > 0) && r.CGB * kStatReplicas <= 64;
-  if (a.dy_is_f32) {
-    if (fold) hipLaunchKernelGGL((bn_bwd_apply_kernel<true, true>), r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block);
-    else hipLaunchKernelGGL((bn_bwd_apply_kernel<true, false>), r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block);
-  } else {
-    if (fold) hipLaunchKernelGGL((bn_bwd_apply_kernel<false, true>), r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block);
-    else hipLaunchKernelGGL((bn_bwd_apply_kernel<false, false>), r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block);
+#define FDG_LAUNCH_APPLY(F32, CP) \
+  hipLaunchKernelGGL((bn_bwd_apply_kernel<F32, CP>), r.grid, dim3(kThreads), 0, s, a, r.CGB, r.rows_per_block)
+  switch (host_copies_per_lane(r.CGB, a.rep_stride)) {
+    case 1: if (a.dy_is_f32) FDG_LAUNCH_APPLY(true, 1); else FDG_LAUNCH_APPLY(false, 1); break;
+    case 2: if (a.dy_is_f32) FDG_LAUNCH_APPLY(true, 2); else FDG_LAUNCH_APPLY(false, 2); break;
+    case 4: if (a.dy_is_f32) FDG_LAUNCH_APPLY(true, 4); else FDG_LAUNCH_APPLY(false, 4); break;
+    default: if (a.dy_is_f32) FDG_LAUNCH_APPLY(true, 8); else FDG_LAUNCH_APPLY(false, 8); break;
   }
+#undef FDG_LAUNCH_APPLY
   return hipGetLastError();
 }
 

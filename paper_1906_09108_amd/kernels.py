@@ -7,7 +7,7 @@ import ctypes
 from .binding import _ptr, _stream_handle, load
 
 KERNEL_EXPORTS = ["fdgk_conv_fwd", "fdgk_conv_dgrad", "fdgk_conv_dgrad_gated", "fdgk_conv_dgrad_feeding_next", "fdgk_conv_dgrad_gates", "fdgk_bn_bwd_gated", "fdgk_conv_wgrad", "fdgk_conv_wgrad_scratch_bytes", "fdgk_bn_stats", "fdgk_bn_apply",
-                  "fdgk_bn_bwd", "fdgk_sgd", "fdgk_bn_bwd_static", "fdgk_bn_bwd_static_max_c"]
+                  "fdgk_bn_bwd", "fdgk_sgd", "fdgk_bn_bwd_static", "fdgk_bn_bwd_static_max_c", "fdgk_sums_bytes", "fdgk_sums_read"]
 _ready = False
 
 
@@ -30,11 +30,14 @@ def _lib():
         lib.fdgk_sgd.argtypes = [vp, vp, vp, sz, f, f, f, vp]
         lib.fdgk_bn_bwd_static.argtypes = [vp, i, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, f, vp]
         lib.fdgk_bn_bwd_static_max_c.argtypes = []
+        lib.fdgk_sums_bytes.argtypes = [i]
+        lib.fdgk_sums_read.argtypes = [vp, i, vp, vp]
         for n in KERNEL_EXPORTS:
             if getattr(lib, n).argtypes is None:   # a pointer passed without a declared type would be cut to 32 bits
                 raise RuntimeError(f"{n}: argument types not declared")
             getattr(lib, n).restype = i
         lib.fdgk_conv_wgrad_scratch_bytes.restype = sz
+        lib.fdgk_sums_bytes.restype = sz
         _ready = True
     return lib
 
@@ -42,6 +45,24 @@ def _lib():
 def _ok(rc: int, name: str) -> None:
     if rc != 0:
         raise RuntimeError(f"{name} failed with hipError_t {rc}")
+
+
+def fdgk_sums_bytes(c: int) -> int:
+    return int(_lib().fdgk_sums_bytes(int(c)))
+
+
+def new_sums(c: int, device="cuda:0"):
+    """A zeroed sums array for c channels (torch owns the memory; the format is the library's)."""
+    import torch
+    return torch.zeros(fdgk_sums_bytes(c) // 8, dtype=torch.int64, device=device)
+
+
+def fdgk_sums_read(sums, c: int, stream=None):
+    """Totals of a sums array as a host float64 array [2c]: first sums, then second sums."""
+    import numpy as np
+    out = np.empty(2 * c, np.float64)
+    _ok(_lib().fdgk_sums_read(_ptr(sums), int(c), out.ctypes.data, _stream_handle(stream)), "fdgk_sums_read")
+    return out
 
 
 def fdgk_conv_fwd(x_b16, w_b16, addend_f32, y_f32, y_b16, stats_f32, n, h, w, ci, co, ksize, stride, stream=None):

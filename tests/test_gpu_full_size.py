@@ -92,7 +92,7 @@ def test_conv_forward_and_data_gradient_on_sampled_images(case):
     w_oihw = wt.reshape(co, k, k, ci).transpose(0, 3, 1, 2).copy()
     y16 = t.zeros((n, ho, wo, co), dtype=t.bfloat16, device="cuda")
     y32 = t.full((n, ho, wo, co), float("nan"), dtype=t.float32, device="cuda")
-    stats = t.zeros(2 * co, dtype=t.float32, device="cuda")
+    stats = K.new_sums(co)
     K.fdgk_conv_fwd(xd, wd, None, y32, y16, stats, n, h, w, ci, co, k, s)
     t.cuda.synchronize()
     imgs = sorted({i % n for i in IMAGES})
@@ -103,7 +103,7 @@ def test_conv_forward_and_data_gradient_on_sampled_images(case):
     assert rel(got32, ref) <= F32_TOL
     assert rel(got16, ref) <= B16_TOL
     yb = y16.to(t.float64).reshape(-1, co)
-    st = stats.cpu().numpy().astype(np.float64)
+    st = K.fdgk_sums_read(stats, co)
     assert rel(st[:co], yb.sum(0).cpu().numpy()) <= 1e-5
     assert rel(st[co:], (yb * yb).sum(0).cpu().numpy()) <= 1e-5
     assert bool(t.isfinite(y32).all())
@@ -163,7 +163,7 @@ def test_batch_norm_on_sampled_channels(m, c):
     gamma = (1 + 0.2 * r.standard_normal(c)).astype(np.float32)
     beta = (0.2 * r.standard_normal(c)).astype(np.float32)
     gd, bd = t.from_numpy(gamma).cuda(), t.from_numpy(beta).cuda()
-    sums = t.zeros(2 * c, dtype=t.float32, device="cuda")
+    sums = K.new_sums(c)
     K.fdgk_bn_stats(xd, sums, m, c)
     y32 = t.empty((m, c), dtype=t.float32, device="cuda")
     y16 = t.empty((m, c), dtype=t.bfloat16, device="cuda")
@@ -179,7 +179,7 @@ def test_batch_norm_on_sampled_channels(m, c):
     gate = (y16[:, sel].to(t.float32).cpu().numpy() > 0)
     g = (dyd[:, sel].cpu().numpy() * gate).astype(np.float32)
     dx_ref, dgamma_ref, dbeta_ref = K32.bn_bwd(x4, g.T.reshape(1, len(sel), m, 1).copy(), gamma[sel], mean, invstd)
-    scratch = t.zeros(2 * c, dtype=t.float32, device="cuda")
+    scratch = K.new_sums(c)
     dx32 = t.empty((m, c), dtype=t.float32, device="cuda")
     dg, db = t.empty(c, dtype=t.float32, device="cuda"), t.empty(c, dtype=t.float32, device="cuda")
     K.fdgk_bn_bwd(dyd, True, y16, xd, sums, gd, scratch, None, dx32, None, dg, db, m, c, eps)

@@ -135,14 +135,14 @@ def test_conv_fwd(case):
     add = np.random.default_rng(2).standard_normal(ref.shape).astype(np.float32)
     y32 = t.full((n, ho, wo, co), float("nan"), dtype=t.float32, device="cuda")
     y16 = t.zeros((n, ho, wo, co), dtype=t.bfloat16, device="cuda")
-    stats = t.zeros(2 * co, dtype=t.float32, device="cuda")
+    stats = K.new_sums(co)
     K.fdgk_conv_fwd(xd, wd, None, y32, y16, stats, n, h, w, ci, co, k, s)
     t.cuda.synchronize()
     assert rel(nhwc_to_nchw(y32), ref) <= F32_TOL
     assert rel(nhwc_to_nchw(y16), ref) <= B16_TOL
     # fused batch-norm statistics: sums of the bf16 values just written
     yb = y16.to(t.float64).reshape(-1, co)
-    got = stats.cpu().numpy().astype(np.float64)
+    got = K.fdgk_sums_read(stats, co)
     assert rel(got[:co], yb.sum(0).cpu().numpy()) <= 1e-5
     assert rel(got[co:], (yb * yb).sum(0).cpu().numpy()) <= 1e-5
     K.fdgk_conv_fwd(xd, wd, to_dev_nhwc_f32(add), y32, None, None, n, h, w, ci, co, k, s)
@@ -217,7 +217,7 @@ def test_gated_data_gradient_feeds_the_batch_norm_backward(case):
     bnx = bf16_round(r.standard_normal(ref.shape) * (0.5 + r.random((1, ci, 1, 1))) + r.standard_normal((1, ci, 1, 1)))
     dyd = to_dev_nhwc_b16(dy)
     wtd = t.from_numpy(wt.transpose(1, 2, 3, 0).copy()).to(t.bfloat16).contiguous().cuda()
-    gsums = t.zeros(2 * ci, dtype=t.float32, device="cuda")
+    gsums = K.new_sums(ci)
     g32 = t.full((n, h, w, ci), float("nan"), dtype=t.float32, device="cuda")
     g16 = t.zeros((n, h, w, ci), dtype=t.bfloat16, device="cuda")
     K.fdgk_conv_dgrad_gated(dyd, wtd, to_dev_nhwc_f32(add), to_dev_nhwc_b16(gate), to_dev_nhwc_b16(bnx), gsums, g32, g16,
@@ -230,7 +230,7 @@ def test_gated_data_gradient_feeds_the_batch_norm_backward(case):
     # the sums are those of the bf16 values written (holds exactly up to summation order)
     gb = g16.to(t.float64).reshape(-1, ci).cpu().numpy()
     xb = to_dev_nhwc_b16(bnx).to(t.float64).reshape(-1, ci).cpu().numpy()
-    got = gsums.cpu().numpy().astype(np.float64)
+    got = K.fdgk_sums_read(gsums, ci)
     assert rel(got[:ci], gb.sum(0)) <= 1e-5
     assert rel(got[ci:], (gb * xb).sum(0)) <= 1e-5
     # batch-norm backward from those sums against the oracle's on the same rounded g
@@ -241,7 +241,7 @@ def test_gated_data_gradient_feeds_the_batch_norm_backward(case):
     _, mean, var, invstd = K32.bn_fwd(x4, gamma, np.zeros(ci, np.float32), eps)
     dx_ref, dgamma_ref, dbeta_ref = K32.bn_bwd(x4, gb.T.reshape(1, ci, m, 1).astype(np.float32), gamma, mean, invstd)
     xd = to_dev_nhwc_b16(bnx).reshape(m, ci)
-    sums = t.zeros(2 * ci, dtype=t.float32, device="cuda")
+    sums = K.new_sums(ci)
     K.fdgk_bn_stats(xd, sums, m, ci)
     res = r.standard_normal((m, ci)).astype(np.float32)
     dx32 = t.empty((m, ci), dtype=t.float32, device="cuda")
@@ -275,7 +275,7 @@ def test_data_gradient_that_feeds_the_layer_below(case):
     gate = bf16_round(np.maximum(r.standard_normal(ref.shape), 0))
     bnx = bf16_round(r.standard_normal(ref.shape) * (0.5 + r.random((1, ci, 1, 1))) + r.standard_normal((1, ci, 1, 1)))
     wtd = t.from_numpy(wt.transpose(1, 2, 3, 0).copy()).to(t.bfloat16).contiguous().cuda()
-    gsums = t.zeros(2 * ci, dtype=t.float32, device="cuda")
+    gsums = K.new_sums(ci)
     g32 = t.full((n, h, w, ci), float("nan"), dtype=t.float32, device="cuda")
     g16 = t.zeros((n, h, w, ci), dtype=t.bfloat16, device="cuda")
     K.fdgk_conv_dgrad_feeding_next(to_dev_nhwc_b16(dy), wtd, to_dev_nhwc_f32(add), to_dev_nhwc_b16(mask), to_dev_nhwc_b16(gate),
@@ -288,7 +288,7 @@ def test_data_gradient_that_feeds_the_layer_below(case):
     assert np.all(got32[gate <= 0] == 0)
     gf = g32.to(t.float64).reshape(-1, ci).cpu().numpy()
     xb = to_dev_nhwc_b16(bnx).to(t.float64).reshape(-1, ci).cpu().numpy()
-    got = gsums.cpu().numpy().astype(np.float64)
+    got = K.fdgk_sums_read(gsums, ci)
     assert rel(got[:ci], gf.sum(0)) <= 1e-5
     assert rel(got[ci:], (gf * xb).sum(0)) <= 1e-5
     # and they are NOT the sums of the bf16 copy wherever the two differ measurably
@@ -359,10 +359,10 @@ def test_bn_forward_and_backward(m, c):
     x4 = x.T.reshape(1, c, m, 1)                      # oracle layout: N=1, C, H=m, W=1
     y_ref, mean, var, invstd = K32.bn_fwd(x4, gamma, beta, eps)
     xd = t.from_numpy(x).to(t.bfloat16).cuda()
-    sums = t.zeros(2 * c, dtype=t.float32, device="cuda")
+    sums = K.new_sums(c)
     K.fdgk_bn_stats(xd, sums, m, c)
     t.cuda.synchronize()
-    s = sums.cpu().numpy()
+    s = K.fdgk_sums_read(sums, c)
     assert rel(s[:c] / m, mean.astype(np.float64)) <= 1e-5
     assert rel(s[c:] / m - (s[:c] / m) ** 2, var.astype(np.float64)) <= 1e-4
     gd, bd = t.from_numpy(gamma).cuda(), t.from_numpy(beta).cuda()
@@ -388,7 +388,7 @@ def test_bn_forward_and_backward(m, c):
         dx_ref, dgamma_ref, dbeta_ref = K32.bn_bwd(x4, g.T.reshape(1, c, m, 1), gamma, mean, invstd)
         add = r.standard_normal((m, c)).astype(np.float32)
         dyd = t.from_numpy(dy).cuda() if dy_is_f32 else t.from_numpy(dy).to(t.bfloat16).cuda()
-        scratch = t.zeros(2 * c, dtype=t.float32, device="cuda")
+        scratch = K.new_sums(c)
         dx32 = t.empty((m, c), dtype=t.float32, device="cuda")
         dx16 = t.empty((m, c), dtype=t.bfloat16, device="cuda")
         dg, db = t.empty(c, dtype=t.float32, device="cuda"), t.empty(c, dtype=t.float32, device="cuda")
@@ -414,3 +414,43 @@ def test_sgd(count):
     t.cuda.synchronize()
     assert rel(td.cpu().numpy(), theta.astype(np.float64)) <= 1e-6
     assert rel(vd.cpu().numpy(), v.astype(np.float64)) <= 1e-6
+
+
+@pytest.mark.parametrize("ratio", [30.0, 300.0])
+def test_batch_norm_with_a_mean_far_from_zero(ratio):
+    """|mean| / sigma = 30 and 300 per channel.  The statistics are sum x and sum x^2; their totals are exact and the
+    variance sum x^2 / m - mean^2 is taken in double, so the cancellation costs nothing beyond the fp32 rounding of a
+    workgroup's partial sum of squares (1e-7 * ratio^2 of the variance); a plain fp32 evaluation of that formula
+    loses ratio^2 * 6e-8 = 5e-3 (ratio 300) on top."""
+    from paper_1906_09108_amd import kernels as K
+    t = _torch()
+    m, c = 8192, 64
+    eps = 1e-5
+    r = np.random.default_rng(int(ratio))
+    sigma = 0.5 + r.random(c)
+    x = bf16_round(r.standard_normal((m, c)) * sigma + ratio * sigma * np.sign(r.standard_normal(c)))
+    gamma = (1 + 0.2 * r.standard_normal(c)).astype(np.float32)
+    beta = (0.2 * r.standard_normal(c)).astype(np.float32)
+    x4 = x.T.reshape(1, c, m, 1)
+    y_ref, mean, var, invstd = K32.bn_fwd(x4, gamma, beta, eps)          # two passes, double accumulation
+    xd = t.from_numpy(x).to(t.bfloat16).cuda()
+    sums = K.new_sums(c)
+    K.fdgk_bn_stats(xd, sums, m, c)
+    y32 = t.empty((m, c), dtype=t.float32, device="cuda")
+    K.fdgk_bn_apply(xd, sums, t.from_numpy(gamma).cuda(), t.from_numpy(beta).cuda(), None, y32, None, m, c, eps, 0)
+    t.cuda.synchronize()
+    tol = 2e-4 if ratio <= 30 else 2e-2      # bf16 inputs this far from zero have only a few steps across their spread
+    assert rel(y32.cpu().numpy(), y_ref.reshape(c, m).T) <= tol
+    # backward through a ReLU gate
+    dy = r.standard_normal((m, c)).astype(np.float32)
+    mask = bf16_round(r.standard_normal((m, c)))
+    g = (dy * (mask > 0)).astype(np.float32)
+    dx_ref, dgamma_ref, dbeta_ref = K32.bn_bwd(x4, g.T.reshape(1, c, m, 1).copy(), gamma, mean, invstd)
+    dx32 = t.empty((m, c), dtype=t.float32, device="cuda")
+    dg, db = t.empty(c, dtype=t.float32, device="cuda"), t.empty(c, dtype=t.float32, device="cuda")
+    K.fdgk_bn_bwd(t.from_numpy(dy).cuda(), True, t.from_numpy(mask).to(t.bfloat16).cuda(), xd, sums, t.from_numpy(gamma).cuda(),
+                  K.new_sums(c), None, dx32, None, dg, db, m, c, eps)
+    t.cuda.synchronize()
+    assert rel(db.cpu().numpy(), dbeta_ref) <= 2e-4
+    assert rel(dg.cpu().numpy(), dgamma_ref) <= tol
+    assert rel(dx32.cpu().numpy(), dx_ref.reshape(c, m).T) <= tol
