@@ -109,14 +109,9 @@ def test_chain_against_the_oracle(K, save_mode):
 
 def test_chain_compounds_the_shrinking_factor():
     """Eq. 16 / Eq. 17 on the device, weights frozen (lr = 0): g_hat(module k; beta) = beta^(K-1-k) g_hat(module k; 1),
-    k counted from 0.  beta = 0.5 scales every intermediate by a power of two, so the two runs differ only through
-    the order of fp32 atomic sums (batch-norm statistics: one atomic per workgroup and channel).  A last-bit
-    difference in such a sum moves a bf16 rounding of some activation (about one per forward at these sizes), and
-    behind it now and then a ReLU gate; in layers this small (256 to 1024 pixels per channel) one gate carries
-    several per cent of a weight-gradient element (1 / sqrt(pixels) of a sum of random-sign terms, more where the
-    loss gradient is constant over an image).  Two runs with the SAME beta differ in the same way (measured: half
-    of the runs, up to 6e-2 in max norm).  A wrong exponent, or a path that misses the factor, is off by 50 % or
-    more in both norms, which is what the bounds are for: 2^-3 in max norm, 2^-5 in relative L2."""
+    k counted from 0.  beta = 0.5 scales every intermediate of the backward by a power of two; every operation of the
+    backward is linear in the gradient, powers of two commute with every rounding, and the sums over workgroups are exact
+    integers (order independent), so the relation holds BIT FOR BIT."""
     t = _torch()
     from paper_1906_09108_amd import FdgChain
     K = 3
@@ -140,8 +135,7 @@ def test_chain_compounds_the_shrinking_factor():
     for k in range(K):
         ref = runs[1.0][k] * 0.5 ** (K - 1 - k)
         assert np.abs(ref).max() > 0
-        assert rel_err(runs[0.5][k], ref) <= 2.0 ** -3 and rel_l2(runs[0.5][k], ref) <= 2.0 ** -5, \
-            (k, rel_err(runs[0.5][k], ref), rel_l2(runs[0.5][k], ref))
+        assert np.array_equal(runs[0.5][k], ref), (k, rel_err(runs[0.5][k], ref), rel_l2(runs[0.5][k], ref))
         if k < K - 1:   # and the factor is there at all
             assert rel_l2(runs[0.5][k], runs[1.0][k]) > 0.4
 
