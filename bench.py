@@ -22,12 +22,32 @@ if ROOT not in sys.path:
 PEAK_MFMA_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 
-# HBM-side traffic measured with rocprofv3 counters for the dominant kernel, per launch (bytes);
-# from the committed summaries under profiles/ (None where not measured)
-TRAFFIC_BYTES = {
-    # profiles/hbm_traffic_conv_kernels_cfg4.md: FETCH_SIZE + WRITE_SIZE, scaled by the 1 GiB copy calibration
-    (4, "conv_patch_kernel<160, 160, 5> 640>640 k3 s1 @8x8"): 103.6e6,
-}
+
+
+def library_source_sha() -> str:
+    """sha256 over the HIP sources of the library: what a stored counter measurement is valid for."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_1906_09108_amd", "csrc", "*.h*"))):
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(config: int, kernel: str):
+    """HBM-side bytes per launch of `kernel` (FETCH_SIZE + WRITE_SIZE of rocprofv3 --pmc, each scaled by what the same
+    counter reads for a plain copy of known size) from profiles/hbm_traffic.json -- or None when that file was measured
+    on other sources than the ones this run uses (it is then stale and says nothing about this build)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        rec = json.load(open(path))
+    except (OSError, ValueError):
+        return None, "not measured"
+    if rec.get("library_source_sha") != library_source_sha():
+        return None, "stale: profiles/hbm_traffic.json was measured on other kernel sources"
+    v = rec.get("bytes_per_launch", {}).get(f"cfg{config}|{kernel}")
+    return (v, rec.get("how", "")) if v is not None else (None, "not measured for this kernel")
 
 
 def parse_args():
@@ -59,7 +79,7 @@ def cpu_baseline(idx: int, sample_batch: int):
     import numpy as np
     import fdg_workloads as W
     from oracle import fdg_oracle
-    n = sample_batch or {1: 128, 2: 128, 3: 128, 4: 64, 5: 32, 6: 64, 7: 32, 8: 32}[idx]   # about 10-30 s of oracle time
+    n = sample_batch or {1: 128, 2: 128, 3: 128, 4: 128, 5: 32, 6: 64, 7: 32, 8: 32}[idx]   # about 10-30 s of oracle time
     spec = W.config(idx, n=n)
     spec.delay = 0
     m = fdg_oracle.OracleModule(spec, np.float32, storage="fp32")
@@ -225,6 +245,19 @@ def main():
     # part of a recorded graph)
     step = eager_step
     torch.cuda.synchronize()
+    if args.graph:
+        # The replays advanced the ring on the device while the library's host counters stayed where the recording
+        # left them: an eager step of THIS module would pop a slot that is not the oldest saved forward.  The
+        # profile is therefore taken on a fresh module of the same shape (same kernels, same sizes).
+        ws_bytes = mod.workspace_bytes
+        mod.close()
+        mod = FdgModule(spec, dev, save_mode=1 if args.replay else 0)
+        mod.set_params(W.make_params(spec))
+        for t in range(spec.delay):
+            mod.forward(xs[t % pool], labels[t % pool], y, stream)
+        for i in range(args.warmup):
+            step(i)
+        torch.cuda.synchronize()
     mod.profile_enable(True)
     for i in range(args.steps):
         step(args.warmup + args.steps + i)
@@ -257,8 +290,8 @@ def main():
     roofline.update({"avg_launch_ms": avg_ms, "calls_per_step": dom["calls"] / args.steps,
                      "share_of_step": dom["total_ms"] / total_ms,
                      "algorithmic_flops_per_launch": dom["flops"] / dom["calls"],
-                     "algorithmic_bytes_per_launch": dom["bytes"] / dom["calls"],
-                     "traffic": TRAFFIC_BYTES.get((args.config, name))})
+                     "algorithmic_bytes_per_launch": dom["bytes"] / dom["calls"]})
+    roofline["traffic"], roofline["traffic_source"] = measured_traffic(args.config, name)
     classes = {k: {"ms_per_step": v["total_ms"] / args.steps, "calls_per_step": v["calls"] / args.steps,
                    "TFLOP/s": (v["flops"] / (v["total_ms"] * 1e-3) / 1e12) if v["flops"] else None,
                    "GB/s": v["bytes"] / (v["total_ms"] * 1e-3) / 1e9}

@@ -31,6 +31,12 @@
  *     (the forward snapshots the weights the update moves); the next fdg_forward after that update; a
  *     fdg_backward_delayed after the forward whose context it pops (only an issue at delay-many steps' distance).
  *     With delay 0, or FDG_SAVE_INPUT_AND_REPLAY, give all calls of a step one stream (or order them fully).
+ *   - Stream capture.  Every entry point may be recorded into a HIP graph (hipStreamBeginCapture on its stream): the
+ *     library allocates nothing, clears memory with kernels and forks / joins its own second stream with events.  A
+ *     step on ONE stream records as it is.  Recording the forward on one stream and the backward side (backward,
+ *     update) on another inside the SAME capture is not supported: the call that would put the second stream of a
+ *     module into a capture returns FDG_ERR_UNSUPPORTED and enqueues nothing.  Record the two streams' work as two
+ *     graphs, or use one stream under capture.
  */
 #ifndef FDG_H_
 #define FDG_H_
@@ -47,7 +53,7 @@ typedef struct fdg_module fdg_module; /* opaque, host memory, library-owned */
 typedef enum {
   FDG_OK = 0,
   FDG_ERR_INVALID_ARG = 1,         /* NULL where a pointer is required, bad descriptor, bad count */
-  FDG_ERR_UNSUPPORTED = 2,         /* a layer shape this build has no kernel for */
+  FDG_ERR_UNSUPPORTED = 2,         /* a layer shape this build has no kernel for; two streams of a module in one capture */
   FDG_ERR_WORKSPACE_TOO_SMALL = 3, /* bytes < fdg_module_workspace_bytes(desc) or misaligned */
   FDG_ERR_QUEUE_FULL = 4,          /* forward with delay+1 contexts outstanding */
   FDG_ERR_QUEUE_EMPTY = 5,         /* backward with no context outstanding */

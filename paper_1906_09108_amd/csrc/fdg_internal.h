@@ -246,6 +246,13 @@ inline uint32_t emit_blocks_for(int Co, int Cip, int T) { return (uint32_t)(((Co
 hipError_t launch_emit_weights(const float* params, bf16_t* warena, const WeightEmitEntry* table_dev, int nconv,
                                int total_blocks, hipStream_t s);
 
+// launch_sgd over the whole parameter arena and the snapshot in one pass: the updated convolution weights are also
+// written as bf16 into warena (both layouts, as launch_emit_weights) and the updated small parameters
+// [small_off, small_off + small_count) as fp32 into small_snap.  conv_blocks = the blocks launch_emit_weights would take.
+hipError_t launch_sgd_emit(float* params, float* mom, const float* grads, bf16_t* warena, float* small_snap,
+                           const WeightEmitEntry* table_dev, int nconv, int conv_blocks, size_t small_off, size_t small_count,
+                           float lr, float mu, float wd, hipStream_t s);
+
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);  // bytes % 16 == 0
 
 // Name of the convolution kernel the calling thread launched last (as a profiler prints it), for the

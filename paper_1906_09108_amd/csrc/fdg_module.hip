@@ -395,8 +395,12 @@ struct fdg_module {
   char* ws = nullptr;
   int64_t seq_fwd = 0, seq_bwd = 0;
   bool has_grad = false;
+  int64_t snapshot_seq = -1;          // the forward with this sequence number finds its weight snapshot already in its slot
+                                      // (written by the update before it); -1: none
   hipStream_t last_stream = nullptr;
   hipStream_t fwd_stream = nullptr;   // the forward's last stream (it may differ from the backward's)
+  unsigned long long fwd_capture = 0, bwd_capture = 0;   // id of the stream capture the last forward / backward-side call
+                                                         // was recorded in (0: it was not being captured)
   char* trace = nullptr;              // attached trace buffer (parity accessors), or nullptr
   std::vector<char> tr_gated;         // per layer: the traced input gradient is already gated by the layer below
   bool tr_fwd_valid = false, tr_bwd_valid = false;
@@ -426,6 +430,22 @@ namespace {
       return FDG_ERR_HIP;                  \
     }                                      \
   } while (0)
+
+// Id of the capture `s` is being recorded into (hipStreamBeginCapture .. EndCapture), 0 if it is not.
+unsigned long long capture_of(hipStream_t s) {
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  unsigned long long id = 0;
+  if (hipStreamGetCaptureInfo(s, &st, &id) != hipSuccess) {
+    (void)hipGetLastError();
+    return 0;
+  }
+  return st == hipStreamCaptureStatusActive ? id : 0;
+}
+// One capture that holds the forward on one stream and the backward side on another is refused (see fdg.h, "Two
+// streams"): `other` / `other_capture` are the stream and capture id of the last call of the other side.
+bool two_streams_in_one_capture(unsigned long long capture, hipStream_t s, unsigned long long other_capture, hipStream_t other) {
+  return capture != 0 && capture == other_capture && s != other;
+}
 
 // views into one saved forward: `base` its slot, `inter` where its intermediates live
 struct SlotView {
@@ -865,18 +885,25 @@ fdg_status fdg_forward(fdg_module* m, const float* x_dev, const int32_t* labels_
   if (p.is_top != (labels_dev != nullptr)) return FDG_ERR_INVALID_ARG;
   if (m->seq_fwd - m->seq_bwd >= p.d.delay + 1) return FDG_ERR_QUEUE_FULL;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const unsigned long long cap = capture_of(s);
+  if (two_streams_in_one_capture(cap, s, m->bwd_capture, m->last_stream)) return FDG_ERR_UNSUPPORTED;
+  m->fwd_capture = cap;
   m->fwd_stream = s;
   FDG_TRY(side_join(m, s));
   SlotView v = view_of(m, m->seq_fwd);
   const int N = p.d.n;
-  // snapshot of the weights this forward uses (Eq. 10 evaluates the backward at these)
-  {
-    ProfScope ps(m, PC_WEIGHT_SNAPSHOT, 0, 4.0 * p.conv_elems + 2.0 * p.warena_elems, s);
-    FDG_TRY(launch_emit_weights(m->params(), v.warena(), reinterpret_cast<const WeightEmitEntry*>(m->ws + p.o_table),
-                                (int)p.convs.size(), (int)p.emit_blocks, s));
+  // snapshot of the weights this forward uses (Eq. 10 evaluates the backward at these), unless the update that produced
+  // them has already left it in this slot
+  if (m->snapshot_seq != m->seq_fwd) {
+    {
+      ProfScope ps(m, PC_WEIGHT_SNAPSHOT, 0, 4.0 * p.conv_elems + 2.0 * p.warena_elems, s);
+      FDG_TRY(launch_emit_weights(m->params(), v.warena(), reinterpret_cast<const WeightEmitEntry*>(m->ws + p.o_table),
+                                  (int)p.convs.size(), (int)p.emit_blocks, s));
+    }
+    if (p.small_count)
+      FDG_TRY(hipMemcpyAsync(v.small(), m->params() + p.small_off, p.small_count * 4, hipMemcpyDeviceToDevice, s));
   }
-  if (p.small_count)
-    FDG_TRY(hipMemcpyAsync(v.small(), m->params() + p.small_off, p.small_count * 4, hipMemcpyDeviceToDevice, s));
+  m->snapshot_seq = -1;
   if (p.is_top) FDG_TRY(hipMemcpyAsync(v.labels(), labels_dev, (size_t)N * 4, hipMemcpyDeviceToDevice, s));
   if (p.replay) FDG_TRY(hipMemcpyAsync(v.xcopy(), x_dev, (size_t)N * p.d.c_in * p.d.h_in * p.d.w_in * 4, hipMemcpyDeviceToDevice, s));
   if (fdg_status st = forward_pass(m, v, x_dev, y_dev, /*replayed=*/false, s); st != FDG_OK) return st;
@@ -890,6 +917,9 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
   if (p.is_top ? grad_out_dev != nullptr : grad_out_dev == nullptr) return FDG_ERR_INVALID_ARG;
   if (m->seq_fwd == m->seq_bwd) return FDG_ERR_QUEUE_EMPTY;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const unsigned long long cap = capture_of(s);
+  if (two_streams_in_one_capture(cap, s, m->fwd_capture, m->fwd_stream)) return FDG_ERR_UNSUPPORTED;
+  m->bwd_capture = cap;
   m->last_stream = s;
   SlotView v = view_of(m, m->seq_bwd);  // the OLDEST saved forward
   const int N = p.d.n;
@@ -1051,11 +1081,26 @@ fdg_status fdg_update(fdg_module* m, float lr, void* hip_stream) {
   if (!m) return FDG_ERR_INVALID_ARG;
   if (!m->has_grad) return FDG_ERR_NO_GRAD;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const unsigned long long cap = capture_of(s);
+  if (two_streams_in_one_capture(cap, s, m->fwd_capture, m->fwd_stream)) return FDG_ERR_UNSUPPORTED;
+  m->bwd_capture = cap;
   m->last_stream = s;
   FDG_TRY(side_join(m, s));
-  {
-    ProfScope ps(m, PC_SGD, 0, 20.0 * m->p.P, s);   // read theta, v, g; write theta, v
-    FDG_TRY(launch_sgd(m->params(), m->mom(), m->grads(), m->p.P, lr, m->p.d.momentum, m->p.d.weight_decay, s));
+  const Plan& p = m->p;
+  if (m->seq_fwd - m->seq_bwd <= p.d.delay) {
+    // The slot of the NEXT forward holds no saved forward that still waits for its backward (the last backward, which
+    // this update is ordered after, was its last reader), so the update also leaves that forward's weight snapshot
+    // there: theta is read once for both.
+    const SlotView v = view_of(m, m->seq_fwd);
+    ProfScope ps(m, PC_SGD, 0, 20.0 * p.P + 2.0 * p.warena_elems + 4.0 * p.small_count, s);
+    FDG_TRY(launch_sgd_emit(m->params(), m->mom(), m->grads(), v.warena(), v.small(),
+                            reinterpret_cast<const WeightEmitEntry*>(m->ws + p.o_table), (int)p.convs.size(), (int)p.emit_blocks,
+                            p.small_off, p.small_count, lr, p.d.momentum, p.d.weight_decay, s));
+    m->snapshot_seq = m->seq_fwd;
+  } else {   // the ring is full: the next forward cannot start before another backward, and takes its own snapshot
+    ProfScope ps(m, PC_SGD, 0, 20.0 * p.P, s);   // read theta, v, g; write theta, v
+    FDG_TRY(launch_sgd(m->params(), m->mom(), m->grads(), p.P, lr, p.d.momentum, p.d.weight_decay, s));
+    m->snapshot_seq = -1;
   }
   m->has_grad = false;
   return FDG_OK;
@@ -1098,6 +1143,7 @@ fdg_status fdg_set_params(fdg_module* m, const float* host_src, size_t count) {
   FDG_TRY(hipStreamSynchronize(m->last_stream));
   if (m->fwd_stream != m->last_stream) FDG_TRY(hipStreamSynchronize(m->fwd_stream));
   FDG_TRY(hipMemcpy(m->params(), buf.data(), m->p.P * 4, hipMemcpyHostToDevice));
+  m->snapshot_seq = -1;   // a snapshot the last update left for the next forward is of the old parameters
   FDG_TRY(hipMemset(m->mom(), 0, m->p.P * 4));
   FDG_TRY(hipDeviceSynchronize());
   return FDG_OK;

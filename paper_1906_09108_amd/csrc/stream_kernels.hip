@@ -881,6 +881,111 @@ hipError_t launch_emit_weights(const float* params, bf16_t* warena, const Weight
   return hipGetLastError();
 }
 
+// ---- update and snapshot in one pass ---------------------------------------------------------------
+// Eq. 11 on every parameter AND the bf16 copies of the updated convolution weights that the next forward will use (both
+// layouts), so that theta is read once: 12 bytes read and 8 + 2 * 2 written per convolution weight.  Blocks
+// [0, conv_blocks) take one 64 (co) x 64 (ci) tile of one tap of one convolution, as emit_weights_kernel does: the
+// update runs along ci (16 lanes x float4 = one 256-byte run per output channel), the new value goes to the
+// forward layout [co][tap][cip] from registers and to the data-gradient layout [cip][tap][co] after a transpose
+// through LDS.  The other blocks update the small parameters (batch-norm scale / shift, the classifier) and copy
+// them, fp32, into the snapshot.  Convolutions whose input channels are not a multiple of 4 (the 3-channel stem)
+// take one element per lane instead of four.
+__global__ __launch_bounds__(kThreads) void sgd_emit_kernel(float* __restrict__ params, float* __restrict__ mom,
+                                                            const float* __restrict__ grads, bf16_t* __restrict__ warena,
+                                                            float* __restrict__ small_snap, const WeightEmitEntry* __restrict__ table,
+                                                            int nconv, int conv_blocks, size_t small_off, size_t small_count,
+                                                            float lr, float mu, float wd) {
+  __shared__ float tile[64][65];
+  if ((int)blockIdx.x >= conv_blocks) {   // small parameters: flat, four at a time
+    const size_t i4 = (size_t)(blockIdx.x - conv_blocks) * kThreads + threadIdx.x;
+    if (i4 * 4 >= small_count) return;
+    const size_t i = small_off + i4 * 4;
+    float4 t = *reinterpret_cast<const float4*>(params + i), m = *reinterpret_cast<const float4*>(mom + i);
+    const float4 g = *reinterpret_cast<const float4*>(grads + i);
+    m.x = mu * m.x + (g.x + wd * t.x); m.y = mu * m.y + (g.y + wd * t.y);
+    m.z = mu * m.z + (g.z + wd * t.z); m.w = mu * m.w + (g.w + wd * t.w);
+    t.x -= lr * m.x; t.y -= lr * m.y; t.z -= lr * m.z; t.w -= lr * m.w;
+    *reinterpret_cast<float4*>(mom + i) = m;
+    *reinterpret_cast<float4*>(params + i) = t;
+    *reinterpret_cast<float4*>(small_snap + i4 * 4) = t;
+    return;
+  }
+  int lo = 0, hi = nconv - 1;   // the conv this block belongs to (block_start is ascending)
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (table[mid].block_start <= blockIdx.x) lo = mid; else hi = mid - 1;
+  }
+  const WeightEmitEntry e = table[lo];
+  const int cit = (e.Cip + 63) / 64, cot = (e.Co + 63) / 64;
+  int local = blockIdx.x - e.block_start;
+  const int ci0 = (local % cit) * 64;
+  local /= cit;
+  const int co0 = (local % cot) * 64, t = local / cot;
+  if (e.Ci % 4 == 0) {
+    const int ci = ci0 + 4 * (threadIdx.x & 15);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int col = (threadIdx.x >> 4) + 16 * r, co = co0 + col;
+      float4 th = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (co < e.Co && ci < e.Ci) {
+        const size_t o = e.src_off + ((size_t)co * e.T + t) * e.Ci + ci;
+        th = *reinterpret_cast<const float4*>(params + o);
+        float4 m = *reinterpret_cast<const float4*>(mom + o);
+        const float4 g = *reinterpret_cast<const float4*>(grads + o);
+        m.x = mu * m.x + (g.x + wd * th.x); m.y = mu * m.y + (g.y + wd * th.y);
+        m.z = mu * m.z + (g.z + wd * th.z); m.w = mu * m.w + (g.w + wd * th.w);
+        th.x -= lr * m.x; th.y -= lr * m.y; th.z -= lr * m.z; th.w -= lr * m.w;
+        *reinterpret_cast<float4*>(mom + o) = m;
+        *reinterpret_cast<float4*>(params + o) = th;
+      }
+      const int cl = 4 * (threadIdx.x & 15);
+      tile[col][cl] = th.x; tile[col][cl + 1] = th.y; tile[col][cl + 2] = th.z; tile[col][cl + 3] = th.w;
+      if (co < e.Co && ci < e.Cip)   // the padding channels of the copy are written too (zeros)
+        *reinterpret_cast<uint2*>(warena + e.w_off + ((size_t)co * e.T + t) * e.Cip + ci) =
+            make_uint2(pack_bf16x2(th.x, th.y), pack_bf16x2(th.z, th.w));
+    }
+  } else {
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int r = ty; r < 64; r += 4) {
+      const int co = co0 + r, ci = ci0 + tx;
+      float th = 0.f;
+      if (co < e.Co && ci < e.Ci) {
+        const size_t o = e.src_off + ((size_t)co * e.T + t) * e.Ci + ci;
+        th = params[o];
+        const float m = mu * mom[o] + (grads[o] + wd * th);
+        th -= lr * m;
+        mom[o] = m;
+        params[o] = th;
+      }
+      tile[r][tx] = th;
+      if (co < e.Co && ci < e.Cip) warena[e.w_off + ((size_t)co * e.T + t) * e.Cip + ci] = (bf16_t)th;
+    }
+  }
+  __syncthreads();
+  // data-gradient layout: 8 consecutive output channels of one input channel per lane (16 bytes)
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    const int cil = (threadIdx.x >> 3) + 32 * r, ci = ci0 + cil, col = 8 * (threadIdx.x & 7), co = co0 + col;
+    if (ci < e.Cip && co < e.Co) {   // Co is a multiple of 8: a group of 8 exists or does not
+      float f[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) f[j] = tile[col + j][cil];
+      *reinterpret_cast<uint4*>(warena + e.wt_off + ((size_t)ci * e.T + t) * e.Co + co) = pack8(f);
+    }
+  }
+}
+hipError_t launch_sgd_emit(float* params, float* mom, const float* grads, bf16_t* warena, float* small_snap,
+                           const WeightEmitEntry* table_dev, int nconv, int conv_blocks, size_t small_off, size_t small_count,
+                           float lr, float mu, float wd, hipStream_t s) {
+  if (small_off % 4 != 0 || small_count % 4 != 0 || conv_blocks < 0) return hipErrorInvalidValue;
+  const size_t small_blocks = (small_count / 4 + kThreads - 1) / kThreads;
+  const size_t blocks = (size_t)conv_blocks + small_blocks;
+  if (blocks == 0) return hipSuccess;
+  hipLaunchKernelGGL(sgd_emit_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, s, params, mom, grads, warena, small_snap, table_dev,
+                     nconv, conv_blocks, small_off, small_count, lr, mu, wd);
+  return hipGetLastError();
+}
+
 // ---- fills ------------------------------------------------------------------------------------------
 __global__ void fill_zero_kernel(uint4* p, size_t n16) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
