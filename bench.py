@@ -67,6 +67,12 @@ def parse_args():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run 3 plain device copies of 1 GiB (float32): the known traffic a profiler's HBM counters "
                          "are scaled by")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="weight gradients on the caller's stream (fdg_overlap_enable(0)): for an external profiler's kernel "
+                         "trace, in which a kernel's duration should be its own")
+    ap.add_argument("--copy-reference", action="store_true",
+                    help="instead of the module step: time plain device copies (torch's copy kernel) of the sizes the "
+                         "batch-norm passes of the configuration move; what a pass over a tensor of that size can reach")
     ap.add_argument("--cpu-sample-batch", type=int, default=0, help="batch of the oracle sample (0 = pick by config)")
     ap.add_argument("--chain", type=int, default=0, metavar="K",
                     help="instead of the module step: time one iteration of Algorithm I for the whole WRN-28-10 cut "
@@ -92,6 +98,37 @@ def cpu_baseline(idx: int, sample_batch: int):
     dt = time.perf_counter() - t0
     return {"value": n / dt, "unit": "images/s", "cores": fdg_oracle.num_threads(), "kind": "oracle",
             "sample": f"same layers at batch {n} (of {W.config(idx).n}), 1 step forward+backward+update, {dt:.1f} s"}
+
+
+def copy_reference(args):
+    """A batch-norm pass reads a tensor and writes one of the same size; these tensors are small against the chip (10 to
+    40 MB), so the time of a launch is mostly ramp-up and the latency of one round of memory accesses.  A plain copy of
+    the same bytes is the yardstick: what the memory system gives ANY kernel that moves so little."""
+    import torch
+    import fdg_workloads as W
+    spec = W.config(args.config)
+    dev = torch.device("cuda:0")
+    sizes = sorted({2 * n * c * h * w for (n, c, h, w) in spec.activation_shapes()})   # bf16 NHWC activations
+    sizes += [4 * sizes[-1], 16 * sizes[-1]]
+    out = []
+    for nbytes in sizes:
+        n = nbytes // 2
+        # a ring of buffers, so that a copy does not find its source in L2 from the copy before
+        ring = [(torch.ones(n, dtype=torch.bfloat16, device=dev), torch.empty(n, dtype=torch.bfloat16, device=dev)) for _ in range(8)]
+        for s, d in ring:
+            d.copy_(s)
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(40)]
+        for i, (a, b) in enumerate(evs):
+            s, d = ring[i % 8]
+            a.record()
+            d.copy_(s)
+            b.record()
+        torch.cuda.synchronize()
+        us = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)[20]
+        out.append({"read_MB": nbytes / 1e6, "written_MB": nbytes / 1e6, "median_us": us, "GB/s": 2 * nbytes / us * 1e-3})
+        del ring
+    print(json.dumps({"what": "plain device copies of the sizes of %s's activations (bf16), event-timed" % spec.name, "copies": out}))
 
 
 def chain_bench(args):
@@ -146,6 +183,8 @@ def main():
         sys.exit(2)
     if args.chain:
         return chain_bench(args)
+    if args.copy_reference:
+        return copy_reference(args)
     import numpy as np
     import torch
     import fdg_workloads as W
@@ -163,6 +202,8 @@ def main():
         del src, dst
     mod = FdgModule(spec, dev, save_mode=1 if args.replay else 0)
     mod.set_params(W.make_params(spec))
+    if args.no_overlap:
+        mod.overlap_enable(False)
 
     # a small pool of resident inputs, cycled, so consecutive steps do not re-read the same lines
     pool = 4

@@ -264,6 +264,11 @@ typedef struct {
   double bytes;
 } fdg_profile_entry;
 fdg_status fdg_profile_enable(fdg_module* m, int enable);
+/* Weight gradients normally run on a second stream of the module and overlap the rest of the backward (they depend only
+ * on tensors that exist when they are launched, and only the update reads their result).  enable = 0 keeps them on
+ * the caller's stream -- a kernel's duration in an external profiler's trace is then its own -- enable = 1 (the
+ * default) restores the overlap.  Results are the same bits either way.  Synchronises the module's streams.          */
+fdg_status fdg_overlap_enable(fdg_module* m, int enable);
 fdg_status fdg_profile_read(fdg_module* m, fdg_profile_entry* host_out, int32_t capacity, int32_t* count);
 
 const char* fdg_status_string(fdg_status s);

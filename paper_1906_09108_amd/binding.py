@@ -47,7 +47,7 @@ EXPORTS = ["fdg_module_workspace_bytes", "fdg_module_create", "fdg_module_worksp
            "fdg_destroy", "fdg_param_count", "fdg_set_params", "fdg_get_params", "fdg_get_grads", "fdg_get_momentum",
            "fdg_bn_stat_count", "fdg_get_bn_running", "fdg_output_shape", "fdg_queue_state", "fdg_status_string",
            "fdg_profile_enable", "fdg_profile_read", "fdg_input_shape", "fdg_module_traits",
-           "fdg_saved_read", "fdg_trace_bytes", "fdg_trace_attach", "fdg_trace_read",
+           "fdg_saved_read", "fdg_trace_bytes", "fdg_trace_attach", "fdg_trace_read", "fdg_overlap_enable",
            "fdg_chain_mailbox_bytes", "fdg_chain_create", "fdg_chain_step", "fdg_chain_state", "fdg_chain_destroy"]
 
 
@@ -80,6 +80,7 @@ def load() -> ctypes.CDLL:
     lib.fdg_queue_state.restype = i32
     lib.fdg_status_string.argtypes, lib.fdg_status_string.restype = [i32], ctypes.c_char_p
     lib.fdg_profile_enable.argtypes, lib.fdg_profile_enable.restype = [vp, i32], i32
+    lib.fdg_overlap_enable.argtypes, lib.fdg_overlap_enable.restype = [vp, i32], i32
     lib.fdg_profile_read.argtypes = [vp, ctypes.POINTER(fdg_profile_entry), i32, ctypes.POINTER(i32)]
     lib.fdg_profile_read.restype = i32
     lib.fdg_input_shape.argtypes, lib.fdg_input_shape.restype = [vp, ctypes.POINTER(i32 * 4)], i32
@@ -307,6 +308,11 @@ class FdgModule:
         st = load().fdg_profile_enable(self.handle, int(bool(enable)))
         if st != FDG_OK:
             raise FdgError(st, "fdg_profile_enable")
+
+    def overlap_enable(self, enable: bool) -> None:
+        st = load().fdg_overlap_enable(self.handle, int(bool(enable)))
+        if st != FDG_OK:
+            raise FdgError(st, "fdg_overlap_enable")
 
     def profile_read(self) -> list:
         """[dict(name, kernel, calls, total_ms, flops, bytes)]: one entry per kernel class and, for

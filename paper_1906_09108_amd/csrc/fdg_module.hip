@@ -378,6 +378,7 @@ struct SideStream {
   Reader readers[4];
   bool busy = false;
   bool usable = false;
+  bool wanted = true;    // fdg_overlap_enable
   ~SideStream() {
     if (stream) { (void)hipStreamSynchronize(stream); (void)hipStreamDestroy(stream); }
     if (ready) (void)hipEventDestroy(ready);
@@ -557,7 +558,7 @@ hipError_t mconv_dgrad(const fdg_module* m, const ConvInfo& c, const bf16_t* dy,
 hipError_t mconv_wgrad(const fdg_module* m, const ConvInfo& c, const bf16_t* x, const bf16_t* dy, hipStream_t s) {
   const double bytes = 2 * conv_in_elems(c.sh) + 2 * conv_out_elems(c.sh) + 4.0 * c.sh.Co * c.sh.T * c.sh.Ci;
   SideStream& sd = m->side;
-  if (sd.usable && !m->prof.on) {   // while timing kernels everything stays on one stream: a kernel's time is its own
+  if (sd.usable && sd.wanted && !m->prof.on) {   // while timing kernels everything stays on one stream: a kernel's time is its own
     hipError_t e = hipEventRecord(sd.ready, s);
     if (e == hipSuccess) e = hipStreamWaitEvent(sd.stream, sd.ready, 0);
     if (e != hipSuccess) return e;
@@ -1352,6 +1353,14 @@ fdg_status fdg_profile_enable(fdg_module* m, int enable) {
   if (m->fwd_stream != m->last_stream) FDG_TRY(hipStreamSynchronize(m->fwd_stream));
   m->prof.reset();
   m->prof.on = enable != 0;
+  return FDG_OK;
+}
+
+fdg_status fdg_overlap_enable(fdg_module* m, int enable) {
+  if (!m) return FDG_ERR_INVALID_ARG;
+  if (fdg_status st = sync_streams(m); st != FDG_OK) return st;
+  if (m->side.stream) FDG_TRY(hipStreamSynchronize(m->side.stream));
+  m->side.wanted = enable != 0;
   return FDG_OK;
 }
 

@@ -63,3 +63,36 @@ def test_two_runs_give_the_same_bits(name):
            for (la, ia, va), (_, _, vb) in zip(a, b) if not np.array_equal(va, vb)]
     assert not bad, "\n".join(bad)
     assert all(np.all(np.isfinite(v)) for _, _, v in a)
+
+
+@pytest.mark.parametrize("name", ["cfg4_n8", "cfg8_n25", "ragged"])
+def test_weight_gradients_on_the_callers_stream_give_the_same_bits(name):
+    """fdg_overlap_enable(m, 0) keeps the weight gradients on the caller's stream instead of the module's second one:
+    the same kernels on the same operands, so the same bits."""
+    spec = CASES[name]()
+    print("overlap on/off case", name, flush=True)
+
+    def run(overlap):
+        import torch as t
+        from paper_1906_09108_amd import FdgModule
+        dev = t.device("cuda:0")
+        m = FdgModule(spec)
+        m.overlap_enable(overlap)
+        m.set_params(W.make_params(spec, 3, perturb_bn=True))
+        gin = None if spec.is_bottom else t.empty(spec.input_shape(), dtype=t.float32, device=dev)
+        out = []
+        for it in range(spec.delay + 2):
+            x, lab = W.make_input(spec, it, 3), W.make_labels(spec, it, 3)
+            m.forward(t.from_numpy(x).to(dev), None if lab is None else t.from_numpy(lab).to(dev))
+            if it < spec.delay:
+                continue
+            g = W.make_grad_out(spec, it - spec.delay, 3)
+            m.backward_delayed(None if g is None else t.from_numpy(g).to(dev), gin)
+            out.append(m.get_grads())
+            m.update(spec.lr)
+            out.append(m.get_params())
+        m.close()
+        return out
+    a, b = run(True), run(False)
+    assert all(np.array_equal(u, v) for u, v in zip(a, b))
+    assert all(np.all(np.isfinite(u)) for u in a)
