@@ -303,14 +303,21 @@ class OracleModule:
     descriptor (n, c_in, h_in, w_in, layers[kind,c_in,c_out,stride], delay, is_bottom, num_classes,
     beta, momentum, weight_decay, bn_eps, bn_momentum)."""
 
-    def __init__(self, spec, dtype=np.float32, storage: str = "fp32", save: str = "activations"):
-        """save = "activations": a saved forward keeps every intermediate (the saved graph of Fig. 1(b)).
+    def __init__(self, spec, dtype=np.float32, storage: str = "fp32", save: str = "activations", weights: str = "snapshot"):
+        """weights = "snapshot": the delayed backward runs at the parameters of its own forward (the stale index on
+        every factor of Eq. 10).  weights = "current" is the ablation in which a saved forward keeps no parameters:
+        the backward takes whatever the parameters are when it runs (what a framework that updates weights in place
+        and back-propagates through a saved graph would compute) -- stale activations and batch statistics, current
+        convolution weights, batch-norm scales and classifier weights.
+        save = "activations": a saved forward keeps every intermediate (the saved graph of Fig. 1(b)).
         save = "input": it keeps the module input, the labels and the parameters of that forward only, and
         the delayed backward first runs the same forward again (recomputation as in feature replay,
         Section II, but at the STALE parameters, so that Eq. 10 is evaluated as before); running
         statistics move only in forward()."""
-        assert storage in ("fp32", "bf16") and save in ("activations", "input")
+        assert storage in ("fp32", "bf16") and save in ("activations", "input") and weights in ("snapshot", "current")
+        assert not (save == "input" and weights == "current"), "a forward run again needs the parameters it ran with"
         self.save = save
+        self.weights = weights
         self.spec = spec
         self.dt = np.dtype(dtype)
         self.k = Kernels(dtype)
@@ -489,6 +496,8 @@ class OracleModule:
         assert ctx["seq"] == self.seq_bwd
         self.seq_bwd += 1
         k, q, th = self.k, self._q, ctx["theta"]
+        if self.weights == "current":
+            th = self._stored_weights(self.theta.copy())
         if self.save == "input":    # the saved forward again, on its input with its parameters
             _, tapes = self._layers(ctx["x"], ctx["labels"], th, move_running=False)
         else:
