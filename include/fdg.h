@@ -125,9 +125,18 @@ fdg_status fdg_module_create(const fdg_module_desc* desc, void* dev_workspace, s
  *                               into ONE set of activations shared by all contexts.  Results are those of
  *                               FDG_SAVE_ACTIVATIONS up to the order of floating-point sums; the running statistics of
  *                               batch normalisation move only in fdg_forward.  Costs one more forward per backward.
+ *   FDG_SAVE_ACTIVATIONS_CURRENT_WEIGHTS : an ABLATION, not the method.  As FDG_SAVE_ACTIVATIONS, but a saved forward
+ *                               keeps no weight snapshot: the module holds ONE bf16 copy of its weights, which follows
+ *                               every fdg_update and fdg_set_params, and the delayed backward reads the convolution
+ *                               weights, batch-norm scales and classifier weights as they are when it runs (stale
+ *                               activations and batch statistics with current weights: what back-propagating through a
+ *                               saved graph gives when weights are updated in place).  Eq. 10 carries the stale index on
+ *                               the parameters too, so for delay >= 1 this is not the gradient of Eq. 10; with delay 0
+ *                               and the call order forward, backward, update it is bit for bit FDG_SAVE_ACTIVATIONS.
+ *                               Saves delay+1 weight copies (2 bytes per parameter and layout each).
  * fdg_module_workspace_bytes / fdg_module_create are the _ex forms with FDG_SAVE_ACTIVATIONS; everything said
  * there holds here.  Any other save_mode: 0 bytes / FDG_ERR_INVALID_ARG.                                          */
-typedef enum { FDG_SAVE_ACTIVATIONS = 0, FDG_SAVE_INPUT_AND_REPLAY = 1 } fdg_save_mode;
+typedef enum { FDG_SAVE_ACTIVATIONS = 0, FDG_SAVE_INPUT_AND_REPLAY = 1, FDG_SAVE_ACTIVATIONS_CURRENT_WEIGHTS = 2 } fdg_save_mode;
 size_t fdg_module_workspace_bytes_ex(const fdg_module_desc* desc, int32_t save_mode);
 fdg_status fdg_module_create_ex(const fdg_module_desc* desc, int32_t save_mode, void* dev_workspace, size_t bytes,
                                 void* hip_stream, fdg_module** out);

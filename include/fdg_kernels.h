@@ -130,6 +130,29 @@ int fdgk_bn_bwd_gated(const void* g_b16, const void* x_b16, const void* sums, co
  *   g' = g + wd*theta;  v = mu*v + g';  theta = theta - lr*v.                                       */
 int fdgk_sgd(float* theta, float* v, const float* g, size_t count, float lr, float mu, float wd, void* hip_stream);
 
+/* ---- classifier head of a top module (Algorithm I: the top module turns z into the loss and starts the backward) ----
+ * All device pointers, fp32 dense unless marked _b16.
+ * fdgk_avgpool:    pooled[n, c] = mean over hw of o_b16[n, hw, c]              (c % 8 == 0, n <= 65535)
+ * fdgk_fc_fwd:     logits[n, j] = sum_c pooled[n, c] w[j, c] + b[j]
+ * fdgk_softmax_ce: y[0] = mean_n (logsumexp(logits[n, :]) - logits[n, label_n]), y[1 + n*j_count + j] = logits[n, j],
+ *                  dlogits[n, j] = (softmax(logits[n, :])[j] - [j == label_n]) / n_count; a label outside 0 .. j_count-1 is clamped
+ * fdgk_fc_bwd:     dw[j, c] = sum_n dlogits[n, j] pooled[n, c];  db[j] = sum_n dlogits[n, j];  dpooled[n, c] = sum_j dlogits[n, j] w[j, c]
+ * fdgk_pool_bwd:   g[n, hw, c] = dpooled[n, c] / hw_count into g_f32 and / or g_b16 (either may be NULL)                       */
+int fdgk_avgpool(const void* o_b16, float* pooled, int n, int hw, int c, void* hip_stream);
+int fdgk_fc_fwd(const float* pooled, const float* w, const float* b, float* logits, int n, int c, int j, void* hip_stream);
+int fdgk_softmax_ce(const float* logits, const int32_t* labels, float* y, float* dlogits, int n, int j, void* hip_stream);
+int fdgk_fc_bwd(const float* pooled, const float* w, const float* dlogits, float* dw, float* db, float* dpooled, int n, int c,
+                int j, void* hip_stream);
+int fdgk_pool_bwd(const float* dpooled, float* g_f32, void* g_b16, int n, int hw, int c, void* hip_stream);
+
+/* ---- layout changes at the module boundary (the C ABI of the module speaks fp32 NCHW, the kernels NHWC) ----
+ * fdgk_nchw_to_nhwc: dst[n, hw, cc] = scale * src[n, cc, hw] for cc < c and 0 for c <= cc < cp (cp = the channel pitch, >= c), into
+ *                    dst_f32 and / or dst_b16 (rounded to nearest even); scale is the shrinking factor beta of Eq. 15 when the
+ *                    tensor is the gradient handed down by the module above, else 1.
+ * fdgk_nhwc_to_nchw: dst[n, cc, hw] = src[n, hw, cc] for cc < c, src with channel pitch cp.                                      */
+int fdgk_nchw_to_nhwc(const float* src, float* dst_f32, void* dst_b16, int n, int c, int hw, int cp, float scale, void* hip_stream);
+int fdgk_nhwc_to_nchw(const float* src, float* dst, int n, int c, int hw, int cp, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -145,7 +145,7 @@ def fdg_module_create(spec, workspace, stream=None) -> int:
     return out.value
 
 
-FDG_SAVE_ACTIVATIONS, FDG_SAVE_INPUT_AND_REPLAY = 0, 1
+FDG_SAVE_ACTIVATIONS, FDG_SAVE_INPUT_AND_REPLAY, FDG_SAVE_ACTIVATIONS_CURRENT_WEIGHTS = 0, 1, 2
 
 
 def fdg_lr_schedule(epoch: int, warmup_epochs: int = 0) -> float:

@@ -54,6 +54,7 @@ struct Plan {
   std::vector<ParamTensor> ptensors;
   bool is_top = false;
   bool replay = false;         // a saved forward is its input and weight snapshot; the backward runs the forward again
+  bool shared_weights = false; // ablation: saved forwards keep no weight snapshot; every pass reads the module's one copy
   int Cp_in = 0;               // channel pitch of the module input copy
   int out_c = 0, out_h = 0, out_w = 0;
   size_t ext_params = 0;       // external parameter count
@@ -71,6 +72,7 @@ struct Plan {
   size_t o_params = 0, o_mom = 0, o_grads = 0, o_bsums = 0, o_running = 0, o_table = 0, o_slots = 0, slot_bytes = 0;
   // per saved forward: weight snapshot, small-parameter snapshot, labels, (replay) the fp32 NCHW input
   size_t s_warena = 0, s_small = 0, s_labels = 0, s_xcopy = 0;
+  size_t o_warena = 0, o_small = 0;   // shared_weights: the module's one bf16 copy of the weights and of the small parameters
   // intermediates: inside every slot, or (replay) once per module at o_inter
   size_t s_sums = 0, s_xin = 0, s_acts = 0, s_pooled = 0, s_dl = 0, s_logits = 0;
   size_t o_inter = 0, inter_bytes = 0;
@@ -85,8 +87,10 @@ struct Plan {
 
 bool build_plan(const fdg_module_desc* desc, int save_mode, Plan& p, fdg_status* why) {
   *why = FDG_ERR_INVALID_ARG;
-  if (save_mode != FDG_SAVE_ACTIVATIONS && save_mode != FDG_SAVE_INPUT_AND_REPLAY) return false;
+  if (save_mode != FDG_SAVE_ACTIVATIONS && save_mode != FDG_SAVE_INPUT_AND_REPLAY &&
+      save_mode != FDG_SAVE_ACTIVATIONS_CURRENT_WEIGHTS) return false;
   p.replay = save_mode == FDG_SAVE_INPUT_AND_REPLAY;
+  p.shared_weights = save_mode == FDG_SAVE_ACTIVATIONS_CURRENT_WEIGHTS;
   if (!desc || !desc->layers || desc->num_layers <= 0) return false;
   if (desc->n <= 0 || desc->c_in <= 0 || desc->h_in <= 0 || desc->w_in <= 0 || desc->delay < 0) return false;
   if (!(desc->beta > 0.f && desc->beta <= 1.f) || !(desc->bn_eps > 0.f)) return false;
@@ -295,8 +299,10 @@ bool build_plan(const fdg_module_desc* desc, int save_mode, Plan& p, fdg_status*
       size_t& o2 = p.replay ? io : so;
       const size_t at = o2; o2 += align_up(bytes, kAlign); return at;
     };
-    p.s_warena = stake(p.warena_elems * 2);
-    p.s_small = stake(p.small_count * 4);
+    if (!p.shared_weights) {
+      p.s_warena = stake(p.warena_elems * 2);
+      p.s_small = stake(p.small_count * 4);
+    }
     if (p.is_top) p.s_labels = stake((size_t)N * 4);
     if (p.replay) p.s_xcopy = stake((size_t)N * desc->c_in * desc->h_in * desc->w_in * 4);
     p.s_sums = itake(p.stat_floats * kStatWords * sizeof(stat_t) * stat_copies);
@@ -312,6 +318,10 @@ bool build_plan(const fdg_module_desc* desc, int save_mode, Plan& p, fdg_status*
   }
   p.o_slots = take(p.slot_bytes * (size_t)(desc->delay + 1));
   p.o_inter = take(p.inter_bytes);
+  if (p.shared_weights) {
+    p.o_warena = take(p.warena_elems * 2);
+    p.o_small = take(p.small_count * 4);
+  }
   for (int i = 0; i < 2; ++i) p.o_S[i] = take(p.maxE * 4);
   for (int i = 0; i < 2; ++i) p.o_G[i] = take(p.maxE * 4);
   for (int i = 0; i < 2; ++i) p.o_GB[i] = take(p.maxE * 2);
@@ -397,6 +407,7 @@ struct fdg_module {
   int64_t seq_fwd = 0, seq_bwd = 0;
   bool has_grad = false;
   int64_t snapshot_seq = -1;          // the forward with this sequence number finds its weight snapshot already in its slot
+  bool shared_valid = false;          // shared_weights: the module's bf16 copy is that of the present parameters
                                       // (written by the update before it); -1: none
   hipStream_t last_stream = nullptr;
   hipStream_t fwd_stream = nullptr;   // the forward's last stream (it may differ from the backward's)
@@ -453,10 +464,10 @@ struct SlotView {
   const fdg_module* m;
   char* base;
   char* inter;
-  bf16_t* warena() const { return reinterpret_cast<bf16_t*>(base + m->p.s_warena); }
+  bf16_t* warena() const { return reinterpret_cast<bf16_t*>(m->p.shared_weights ? m->ws + m->p.o_warena : base + m->p.s_warena); }
   bf16_t* W(const ConvInfo& c) const { return warena() + c.w_off; }
   bf16_t* Wt(const ConvInfo& c) const { return warena() + c.wt_off; }
-  float* small() const { return reinterpret_cast<float*>(base + m->p.s_small); }
+  float* small() const { return reinterpret_cast<float*>(m->p.shared_weights ? m->ws + m->p.o_small : base + m->p.s_small); }
   // snapshot of a small parameter given its offset in the parameter arena
   float* snap(size_t arena_off) const { return small() + (arena_off - m->p.small_off); }
   stat_t* sums(const BnInfo& b) const { return reinterpret_cast<stat_t*>(inter + m->p.s_sums) + b.stat_off * kStatWords; }
@@ -814,6 +825,19 @@ fdg_status forward_pass(fdg_module* m, const SlotView& v, const float* x_dev, fl
 // ------------------------------------------------------------------------------------------------
 // C ABI
 // ------------------------------------------------------------------------------------------------
+// bf16 copy of the present convolution weights (both layouts) and fp32 copy of the small parameters into v's snapshot
+static fdg_status emit_snapshot(fdg_module* m, const SlotView& v, hipStream_t s) {
+  const Plan& p = m->p;
+  {
+    ProfScope ps(m, PC_WEIGHT_SNAPSHOT, 0, 4.0 * p.conv_elems + 2.0 * p.warena_elems, s);
+    FDG_TRY(launch_emit_weights(m->params(), v.warena(), reinterpret_cast<const WeightEmitEntry*>(m->ws + p.o_table),
+                                (int)p.convs.size(), (int)p.emit_blocks, s));
+  }
+  if (p.small_count)
+    FDG_TRY(hipMemcpyAsync(v.small(), m->params() + p.small_off, p.small_count * 4, hipMemcpyDeviceToDevice, s));
+  return FDG_OK;
+}
+
 extern "C" {
 
 size_t fdg_module_workspace_bytes_ex(const fdg_module_desc* desc, int32_t save_mode) {
@@ -895,16 +919,9 @@ fdg_status fdg_forward(fdg_module* m, const float* x_dev, const int32_t* labels_
   const int N = p.d.n;
   // snapshot of the weights this forward uses (Eq. 10 evaluates the backward at these), unless the update that produced
   // them has already left it in this slot
-  if (m->snapshot_seq != m->seq_fwd) {
-    {
-      ProfScope ps(m, PC_WEIGHT_SNAPSHOT, 0, 4.0 * p.conv_elems + 2.0 * p.warena_elems, s);
-      FDG_TRY(launch_emit_weights(m->params(), v.warena(), reinterpret_cast<const WeightEmitEntry*>(m->ws + p.o_table),
-                                  (int)p.convs.size(), (int)p.emit_blocks, s));
-    }
-    if (p.small_count)
-      FDG_TRY(hipMemcpyAsync(v.small(), m->params() + p.small_off, p.small_count * 4, hipMemcpyDeviceToDevice, s));
-  }
+  if (m->p.shared_weights ? !m->shared_valid : m->snapshot_seq != m->seq_fwd) if (fdg_status st = emit_snapshot(m, v, s); st != FDG_OK) return st;
   m->snapshot_seq = -1;
+  m->shared_valid = true;
   if (p.is_top) FDG_TRY(hipMemcpyAsync(v.labels(), labels_dev, (size_t)N * 4, hipMemcpyDeviceToDevice, s));
   if (p.replay) FDG_TRY(hipMemcpyAsync(v.xcopy(), x_dev, (size_t)N * p.d.c_in * p.d.h_in * p.d.w_in * 4, hipMemcpyDeviceToDevice, s));
   if (fdg_status st = forward_pass(m, v, x_dev, y_dev, /*replayed=*/false, s); st != FDG_OK) return st;
@@ -927,6 +944,10 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
   // the backward sums of batch norm accumulate with atomics and start at zero; every gradient is written
   // (not accumulated) by the kernel that produces it
   FDG_TRY(side_join(m, s));
+  if (p.shared_weights && !m->shared_valid) {   // the parameters were set from outside since the copy was made
+    if (fdg_status st = emit_snapshot(m, v, s); st != FDG_OK) return st;
+    m->shared_valid = true;
+  }
   if (p.replay) {   // the saved forward is its input and its weights: run it again into the module's one set of intermediates
     if (fdg_status st = forward_pass(m, v, v.xcopy(), p.is_top ? m->TP() : nullptr, /*replayed=*/true, s); st != FDG_OK) return st;
   }
@@ -1088,7 +1109,8 @@ fdg_status fdg_update(fdg_module* m, float lr, void* hip_stream) {
   m->last_stream = s;
   FDG_TRY(side_join(m, s));
   const Plan& p = m->p;
-  if (m->seq_fwd - m->seq_bwd <= p.d.delay) {
+  if (p.shared_weights || m->seq_fwd - m->seq_bwd <= p.d.delay) {
+    // (Ablation with one copy of the weights per module: that copy follows every update.)
     // The slot of the NEXT forward holds no saved forward that still waits for its backward (the last backward, which
     // this update is ordered after, was its last reader), so the update also leaves that forward's weight snapshot
     // there: theta is read once for both.
@@ -1098,6 +1120,7 @@ fdg_status fdg_update(fdg_module* m, float lr, void* hip_stream) {
                             reinterpret_cast<const WeightEmitEntry*>(m->ws + p.o_table), (int)p.convs.size(), (int)p.emit_blocks,
                             p.small_off, p.small_count, lr, p.d.momentum, p.d.weight_decay, s));
     m->snapshot_seq = m->seq_fwd;
+    m->shared_valid = true;
   } else {   // the ring is full: the next forward cannot start before another backward, and takes its own snapshot
     ProfScope ps(m, PC_SGD, 0, 20.0 * p.P, s);   // read theta, v, g; write theta, v
     FDG_TRY(launch_sgd(m->params(), m->mom(), m->grads(), p.P, lr, p.d.momentum, p.d.weight_decay, s));
@@ -1145,6 +1168,7 @@ fdg_status fdg_set_params(fdg_module* m, const float* host_src, size_t count) {
   if (m->fwd_stream != m->last_stream) FDG_TRY(hipStreamSynchronize(m->fwd_stream));
   FDG_TRY(hipMemcpy(m->params(), buf.data(), m->p.P * 4, hipMemcpyHostToDevice));
   m->snapshot_seq = -1;   // a snapshot the last update left for the next forward is of the old parameters
+  m->shared_valid = false;
   FDG_TRY(hipMemset(m->mom(), 0, m->p.P * 4));
   FDG_TRY(hipDeviceSynchronize());
   return FDG_OK;

@@ -197,4 +197,40 @@ int fdgk_sgd(float* theta, float* v, const float* g, size_t count, float lr, flo
   return (int)launch_sgd(theta, v, g, count, lr, mu, wd, st(hip_stream));
 }
 
+int fdgk_avgpool(const void* o_b16, float* pooled, int n, int hw, int c, void* hip_stream) {
+  if (!o_b16 || !pooled || n <= 0 || hw <= 0 || c <= 0) return (int)hipErrorInvalidValue;
+  return (int)launch_avgpool(static_cast<const bf16_t*>(o_b16), pooled, n, hw, c, st(hip_stream));
+}
+
+int fdgk_fc_fwd(const float* pooled, const float* w, const float* b, float* logits, int n, int c, int j, void* hip_stream) {
+  if (!pooled || !w || !b || !logits || n <= 0 || c <= 0 || j <= 0) return (int)hipErrorInvalidValue;
+  return (int)launch_fc_fwd(pooled, w, b, logits, n, c, j, st(hip_stream));
+}
+
+int fdgk_softmax_ce(const float* logits, const int32_t* labels, float* y, float* dlogits, int n, int j, void* hip_stream) {
+  if (!logits || !labels || !y || !dlogits || n <= 0 || j <= 0) return (int)hipErrorInvalidValue;
+  return (int)launch_softmax_ce(logits, labels, y, dlogits, n, j, st(hip_stream));
+}
+
+int fdgk_fc_bwd(const float* pooled, const float* w, const float* dlogits, float* dw, float* db, float* dpooled, int n, int c,
+                int j, void* hip_stream) {
+  if (!pooled || !w || !dlogits || !dw || !db || !dpooled || n <= 0 || c <= 0 || j <= 0) return (int)hipErrorInvalidValue;
+  return (int)launch_fc_bwd(pooled, w, dlogits, dw, db, dpooled, n, c, j, st(hip_stream));
+}
+
+int fdgk_pool_bwd(const float* dpooled, float* g_f32, void* g_b16, int n, int hw, int c, void* hip_stream) {
+  if (!dpooled || (!g_f32 && !g_b16) || n <= 0 || hw <= 0 || c <= 0) return (int)hipErrorInvalidValue;
+  return (int)launch_pool_bwd(dpooled, g_f32, static_cast<bf16_t*>(g_b16), n, hw, c, st(hip_stream));
+}
+
+int fdgk_nchw_to_nhwc(const float* src, float* dst_f32, void* dst_b16, int n, int c, int hw, int cp, float scale, void* hip_stream) {
+  if (!src || (!dst_f32 && !dst_b16) || n <= 0 || n > 65535 || c <= 0 || hw <= 0 || cp < c) return (int)hipErrorInvalidValue;
+  return (int)launch_nchw_to_nhwc(src, dst_f32, static_cast<bf16_t*>(dst_b16), n, c, hw, cp, scale, st(hip_stream));
+}
+
+int fdgk_nhwc_to_nchw(const float* src, float* dst, int n, int c, int hw, int cp, void* hip_stream) {
+  if (!src || !dst || n <= 0 || n > 65535 || c <= 0 || hw <= 0 || cp < c) return (int)hipErrorInvalidValue;
+  return (int)launch_nhwc_to_nchw(src, dst, n, c, hw, cp, st(hip_stream));
+}
+
 }  // extern "C"

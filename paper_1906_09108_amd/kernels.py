@@ -7,7 +7,8 @@ import ctypes
 from .binding import _ptr, _stream_handle, load
 
 KERNEL_EXPORTS = ["fdgk_conv_fwd", "fdgk_conv_dgrad", "fdgk_conv_dgrad_gated", "fdgk_conv_dgrad_feeding_next", "fdgk_conv_dgrad_gates", "fdgk_bn_bwd_gated", "fdgk_conv_wgrad", "fdgk_conv_wgrad_scratch_bytes", "fdgk_bn_stats", "fdgk_bn_apply",
-                  "fdgk_bn_bwd", "fdgk_sgd", "fdgk_bn_bwd_static", "fdgk_bn_bwd_static_max_c", "fdgk_sums_bytes", "fdgk_sums_read"]
+                  "fdgk_bn_bwd", "fdgk_sgd", "fdgk_bn_bwd_static", "fdgk_bn_bwd_static_max_c", "fdgk_sums_bytes", "fdgk_sums_read",
+                  "fdgk_avgpool", "fdgk_fc_fwd", "fdgk_softmax_ce", "fdgk_fc_bwd", "fdgk_pool_bwd", "fdgk_nchw_to_nhwc", "fdgk_nhwc_to_nchw"]
 _ready = False
 
 
@@ -32,6 +33,13 @@ def _lib():
         lib.fdgk_bn_bwd_static_max_c.argtypes = []
         lib.fdgk_sums_bytes.argtypes = [i]
         lib.fdgk_sums_read.argtypes = [vp, i, vp, vp]
+        lib.fdgk_avgpool.argtypes = [vp, vp, i, i, i, vp]
+        lib.fdgk_fc_fwd.argtypes = [vp, vp, vp, vp, i, i, i, vp]
+        lib.fdgk_softmax_ce.argtypes = [vp, vp, vp, vp, i, i, vp]
+        lib.fdgk_fc_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, vp]
+        lib.fdgk_pool_bwd.argtypes = [vp, vp, vp, i, i, i, vp]
+        lib.fdgk_nchw_to_nhwc.argtypes = [vp, vp, vp, i, i, i, i, f, vp]
+        lib.fdgk_nhwc_to_nchw.argtypes = [vp, vp, i, i, i, i, vp]
         for n in KERNEL_EXPORTS:
             if getattr(lib, n).argtypes is None:   # a pointer passed without a declared type would be cut to 32 bits
                 raise RuntimeError(f"{n}: argument types not declared")
@@ -145,3 +153,38 @@ def fdgk_bn_bwd_static(dy, dy_is_f32, mask_b16, x_b16, sums_f32, gamma, addend_f
 
 def fdgk_sgd(theta, v, g, count, lr, mu, wd, stream=None):
     _ok(_lib().fdgk_sgd(_ptr(theta), _ptr(v), _ptr(g), count, lr, mu, wd, _stream_handle(stream)), "fdgk_sgd")
+
+
+def fdgk_avgpool(o_b16, pooled, n, hw, c, stream=None, check=True):
+    rc = int(_lib().fdgk_avgpool(_ptr(o_b16), _ptr(pooled), n, hw, c, _stream_handle(stream)))
+    if check:
+        _ok(rc, "fdgk_avgpool")
+    return rc
+
+
+def fdgk_fc_fwd(pooled, w, b, logits, n, c, j, stream=None):
+    _ok(_lib().fdgk_fc_fwd(_ptr(pooled), _ptr(w), _ptr(b), _ptr(logits), n, c, j, _stream_handle(stream)), "fdgk_fc_fwd")
+
+
+def fdgk_softmax_ce(logits, labels, y, dlogits, n, j, stream=None):
+    _ok(_lib().fdgk_softmax_ce(_ptr(logits), _ptr(labels), _ptr(y), _ptr(dlogits), n, j, _stream_handle(stream)), "fdgk_softmax_ce")
+
+
+def fdgk_fc_bwd(pooled, w, dlogits, dw, db, dpooled, n, c, j, stream=None):
+    _ok(_lib().fdgk_fc_bwd(_ptr(pooled), _ptr(w), _ptr(dlogits), _ptr(dw), _ptr(db), _ptr(dpooled), n, c, j,
+                           _stream_handle(stream)), "fdgk_fc_bwd")
+
+
+def fdgk_pool_bwd(dpooled, g_f32, g_b16, n, hw, c, stream=None):
+    _ok(_lib().fdgk_pool_bwd(_ptr(dpooled), _ptr(g_f32), _ptr(g_b16), n, hw, c, _stream_handle(stream)), "fdgk_pool_bwd")
+
+
+def fdgk_nchw_to_nhwc(src, dst_f32, dst_b16, n, c, hw, cp, scale=1.0, stream=None, check=True):
+    rc = int(_lib().fdgk_nchw_to_nhwc(_ptr(src), _ptr(dst_f32), _ptr(dst_b16), n, c, hw, cp, scale, _stream_handle(stream)))
+    if check:
+        _ok(rc, "fdgk_nchw_to_nhwc")
+    return rc
+
+
+def fdgk_nhwc_to_nchw(src, dst, n, c, hw, cp, stream=None):
+    _ok(_lib().fdgk_nhwc_to_nchw(_ptr(src), _ptr(dst), n, c, hw, cp, _stream_handle(stream)), "fdgk_nhwc_to_nchw")

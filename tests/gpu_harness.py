@@ -143,9 +143,10 @@ def run_side_by_side(spec, steps: int, seed: int = 0, perturb_bn: bool = True, b
     from paper_1906_09108_amd import FdgModule
 
     theta0 = W.make_params(spec, seed, perturb_bn=perturb_bn)
-    same = OracleModule(spec, np.float32, storage="bf16")
-    noisy = with_summation_noise(OracleModule(spec, np.float32, storage="bf16"), seed + 1000)
-    plain = OracleModule(spec, np.float32, storage="fp32")
+    wmode = "current" if save_mode == 2 else "snapshot"     # FDG_SAVE_ACTIVATIONS_CURRENT_WEIGHTS: the ablation
+    same = OracleModule(spec, np.float32, storage="bf16", weights=wmode)
+    noisy = with_summation_noise(OracleModule(spec, np.float32, storage="bf16", weights=wmode), seed + 1000)
+    plain = OracleModule(spec, np.float32, storage="fp32", weights=wmode)
     gpu = FdgModule(spec, device, save_mode=save_mode)
     for m in (same, noisy, plain, gpu):
         m.set_params(theta0)

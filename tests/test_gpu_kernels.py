@@ -454,3 +454,113 @@ def test_batch_norm_with_a_mean_far_from_zero(ratio):
     assert rel(db.cpu().numpy(), dbeta_ref) <= 2e-4
     assert rel(dg.cpu().numpy(), dgamma_ref) <= tol
     assert rel(dx32.cpu().numpy(), dx_ref.reshape(c, m).T) <= tol
+
+
+# ---- classifier head and layout kernels ---------------------------------------------------------------------------
+HEAD_CASES = [  # n, h, w, c, classes
+    (128, 8, 8, 640, 10),     # WRN-28-10 head at its full size (the bench workload)
+    (16, 8, 8, 64, 10),       # ResNet-110 head
+    (5, 7, 7, 2048, 200),     # ResNet-101 head, ragged batch
+    (3, 4, 4, 512, 200),      # ResNet-18 head at Tiny-ImageNet resolution
+    (1, 1, 1, 8, 2),
+]
+
+
+@pytest.mark.parametrize("case", HEAD_CASES)
+def test_head_kernels_one_by_one(case):
+    """Average pool, fully connected layer, softmax cross-entropy and their backward kernels, each on the same inputs as the
+    oracle's loop for it (the head of a top module: it produces the loss and the first gradient of Eq. 8)."""
+    from paper_1906_09108_amd import kernels as K
+    t = _torch()
+    n, h, w, c, J = case
+    print("head case", case, flush=True)
+    rng = np.random.default_rng(100 + c + n)
+    o = bf16_round(rng.standard_normal((n, c, h, w)).astype(np.float32) + 0.3)
+    Wt = (rng.standard_normal((J, c)) / np.sqrt(c)).astype(np.float32)
+    b = (0.1 * rng.standard_normal(J)).astype(np.float32)
+    labels = rng.integers(0, J, n).astype(np.int32)
+    dev = "cuda:0"
+    # pool
+    pooled = t.empty((n, c), dtype=t.float32, device=dev)
+    K.fdgk_avgpool(to_dev_nhwc_b16(o), pooled, n, h * w, c)
+    p_ref = K32.avgpool_fwd(o)
+    assert rel(pooled.cpu().numpy(), p_ref) <= 1e-5
+    # fully connected, on the oracle's pooled features
+    p_dev = t.from_numpy(p_ref).to(dev)
+    W_dev, b_dev = t.from_numpy(Wt).to(dev), t.from_numpy(b).to(dev)
+    logits = t.empty((n, J), dtype=t.float32, device=dev)
+    K.fdgk_fc_fwd(p_dev, W_dev, b_dev, logits, n, c, J)
+    l_ref = K32.fc_fwd(p_ref, Wt, b)
+    assert rel(logits.cpu().numpy(), l_ref) <= 1e-5
+    # loss
+    y = t.empty(1 + n * J, dtype=t.float32, device=dev)
+    dl = t.empty((n, J), dtype=t.float32, device=dev)
+    K.fdgk_softmax_ce(t.from_numpy(l_ref).to(dev), t.from_numpy(labels).to(dev), y, dl, n, J)
+    loss_ref, dl_ref = K32.softmax_ce(l_ref, labels)
+    yh = y.cpu().numpy()
+    assert abs(float(yh[0]) - loss_ref) <= 1e-5 * max(1.0, abs(loss_ref))
+    assert np.array_equal(yh[1:].reshape(n, J), l_ref)            # the logits are handed through unchanged
+    assert rel(dl.cpu().numpy(), dl_ref) <= 1e-5
+    # backward of the fully connected layer
+    dW, db, dp = t.empty((J, c), dtype=t.float32, device=dev), t.empty(J, dtype=t.float32, device=dev), t.empty((n, c), dtype=t.float32, device=dev)
+    K.fdgk_fc_bwd(p_dev, W_dev, t.from_numpy(dl_ref).to(dev), dW, db, dp, n, c, J)
+    dW_ref, db_ref, dp_ref = K32.fc_bwd(p_ref, Wt, dl_ref)
+    assert rel(dW.cpu().numpy(), dW_ref) <= 1e-5
+    # db[j] = sum_n dl[n, j] is a sum of terms of both signs that nearly cancel (a softmax row sums to one): absolute bar
+    assert np.abs(db.cpu().numpy() - db_ref).max() <= 1e-6
+    assert rel(dp.cpu().numpy(), dp_ref) <= 1e-5
+    # backward of the pool: both outputs
+    g32 = t.empty((n, h, w, c), dtype=t.float32, device=dev)
+    g16 = t.empty((n, h, w, c), dtype=t.bfloat16, device=dev)
+    K.fdgk_pool_bwd(t.from_numpy(dp_ref).to(dev), g32, g16, n, h * w, c)
+    g_ref = K32.avgpool_bwd(dp_ref, (n, c, h, w))
+    assert rel(nhwc_to_nchw(g32), g_ref) <= 1e-6
+    assert np.array_equal(nhwc_to_nchw(g16), bf16_round(nhwc_to_nchw(g32)))   # the bf16 copy is the rounded fp32 value
+
+
+def test_avgpool_refuses_a_channel_count_it_has_no_vector_loads_for():
+    from paper_1906_09108_amd import kernels as K
+    t = _torch()
+    o = t.zeros((2, 4, 12), dtype=t.bfloat16, device="cuda:0")
+    pooled = t.zeros((2, 12), dtype=t.float32, device="cuda:0")
+    assert K.fdgk_avgpool(o, pooled, 2, 4, 12, check=False) != 0
+
+
+LAYOUT_CASES = [  # n, c, h, w, channel pitch
+    (128, 320, 16, 16, 320),   # the input of the bench workload's module
+    (4, 3, 32, 32, 8),         # an image batch: 3 channels padded to 8
+    (3, 24, 17, 15, 24),       # ragged tiles both ways
+    (2, 10, 5, 7, 16),
+    (1, 1, 1, 1, 8),
+]
+
+
+@pytest.mark.parametrize("case", LAYOUT_CASES)
+def test_layout_kernels(case):
+    """NCHW fp32 -> NHWC (fp32 and bf16, scaled by beta of Eq. 15, padding channels zero) and back: moves and one rounding,
+    so the results are exact."""
+    from paper_1906_09108_amd import kernels as K
+    t = _torch()
+    n, c, h, w, cp = case
+    print("layout case", case, flush=True)
+    rng = np.random.default_rng(7 + c)
+    x = rng.standard_normal((n, c, h, w)).astype(np.float32)
+    src = t.from_numpy(x).cuda()
+    for scale in (1.0, 0.5, 0.2):
+        d32 = t.full((n, h, w, cp), 7.0, dtype=t.float32, device="cuda:0")
+        d16 = t.full((n, h, w, cp), 7.0, dtype=t.bfloat16, device="cuda:0")
+        K.fdgk_nchw_to_nhwc(src, d32, d16, n, c, h * w, cp, scale)
+        want = np.zeros((n, h, w, cp), np.float32)
+        want[..., :c] = (x * np.float32(scale)).transpose(0, 2, 3, 1)
+        got32 = d32.cpu().numpy()
+        assert np.array_equal(got32, want)
+        assert np.array_equal(d16.to(t.float32).cpu().numpy(), bf16_round(want))
+        back = t.full((n, c, h, w), 7.0, dtype=t.float32, device="cuda:0")
+        K.fdgk_nhwc_to_nchw(d32, back, n, c, h * w, cp)
+        assert np.array_equal(back.cpu().numpy(), x * np.float32(scale))
+    # only one of the two outputs
+    d16 = t.full((n, h, w, cp), 7.0, dtype=t.bfloat16, device="cuda:0")
+    K.fdgk_nchw_to_nhwc(src, None, d16, n, c, h * w, cp, 1.0)
+    assert np.array_equal(d16.to(t.float32).cpu().numpy()[..., :c], bf16_round(x.transpose(0, 2, 3, 1)))
+    assert K.fdgk_nchw_to_nhwc(src, None, None, n, c, h * w, cp, 1.0, check=False) != 0
+    assert K.fdgk_nchw_to_nhwc(src, None, d16, n, c, h * w, c - 1, 1.0, check=False) != 0

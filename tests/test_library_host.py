@@ -66,7 +66,10 @@ def test_workspace_bytes_when_a_saved_forward_is_its_input(idx):
     step_full = binding.fdg_module_workspace_bytes(deeper) - full
     step_replay = binding.fdg_module_workspace_bytes_ex(deeper, binding.FDG_SAVE_INPUT_AND_REPLAY) - replay
     assert 0 < step_replay < step_full
-    for bad_mode in (-1, 2, 7):
+    shared = binding.fdg_module_workspace_bytes_ex(spec, binding.FDG_SAVE_ACTIVATIONS_CURRENT_WEIGHTS)
+    assert shared > 0 and shared % 256 == 0
+    assert (shared < full) if spec.delay >= 1 else (shared <= full + 512)   # one weight copy instead of delay + 1
+    for bad_mode in (-1, 3, 7):
         assert binding.fdg_module_workspace_bytes_ex(spec, bad_mode) == 0
     lib = binding.load()
     out = ctypes.c_void_p()
