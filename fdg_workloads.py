@@ -27,9 +27,13 @@ BASIC_PREACT = 2
 HEAD_POSTACT = 3
 HEAD_PREACT = 4
 BOTTLENECK_POSTACT = 5
+STEM_POOL = 6            # ImageNet-style stem: 7x7 convolution stride 2 + BN + ReLU + 3x3 max-pool stride 2 (stride field = 4)
+INVERTED_RESIDUAL = 7    # MobileNet-v2 block: 1x1 expand (x6) + BN + ReLU6, 3x3 depthwise (stride) + BN + ReLU6, 1x1 + BN
 
 KIND_NAMES = {STEM: "stem", BASIC_POSTACT: "basic_postact", BASIC_PREACT: "basic_preact",
-              HEAD_POSTACT: "head_postact", HEAD_PREACT: "head_preact", BOTTLENECK_POSTACT: "bottleneck_postact"}
+              HEAD_POSTACT: "head_postact", HEAD_PREACT: "head_preact", BOTTLENECK_POSTACT: "bottleneck_postact",
+              STEM_POOL: "stem_pool", INVERTED_RESIDUAL: "inverted_residual"}
+EXPANSION = 6            # channels inside an inverted residual block per input channel (MobileNet-v2's t)
 
 
 @dataclass(frozen=True)
@@ -49,8 +53,14 @@ class Layer:
 
     @property
     def c_mid(self) -> int:
-        """Channels inside a bottleneck block: a quarter of its output channels."""
-        return self.c_out // 4
+        """Channels inside a bottleneck block: a quarter of its output channels; inside an inverted residual block:
+        EXPANSION times its input channels."""
+        return EXPANSION * self.c_in if self.kind == INVERTED_RESIDUAL else self.c_out // 4
+
+    @property
+    def adds_input(self) -> bool:
+        """An inverted residual block adds its input to its output when shapes allow (no projection otherwise)."""
+        return self.kind == INVERTED_RESIDUAL and self.stride == 1 and self.c_in == self.c_out
 
 
 @dataclass
@@ -136,6 +146,17 @@ def param_shapes(spec: ModuleSpec) -> List[Tuple[str, Tuple[int, ...], str]]:
                     (p + "conv2.w", (L.c_out, L.c_out, 3, 3), "conv")]
             if L.projects:
                 out += [(p + "proj.w", (L.c_out, L.c_in, 1, 1), "conv")]
+        elif L.kind == STEM_POOL:
+            out += [(p + "conv.w", (L.c_out, L.c_in, 7, 7), "conv"),
+                    (p + "bn.gamma", (L.c_out,), "gamma"), (p + "bn.beta", (L.c_out,), "beta")]
+        elif L.kind == INVERTED_RESIDUAL:
+            cm = L.c_mid
+            out += [(p + "conv1.w", (cm, L.c_in, 1, 1), "conv"),
+                    (p + "bn1.gamma", (cm,), "gamma"), (p + "bn1.beta", (cm,), "beta"),
+                    (p + "conv2.w", (cm, 1, 3, 3), "conv"),          # depthwise: one 3x3 filter per channel
+                    (p + "bn2.gamma", (cm,), "gamma"), (p + "bn2.beta", (cm,), "beta"),
+                    (p + "conv3.w", (L.c_out, cm, 1, 1), "conv"),
+                    (p + "bn3.gamma", (L.c_out,), "gamma"), (p + "bn3.beta", (L.c_out,), "beta")]
         elif L.kind == HEAD_POSTACT:
             out += [(p + "fc.w", (spec.num_classes, L.c_in), "fc_w"), (p + "fc.b", (spec.num_classes,), "fc_b")]
         elif L.kind == HEAD_PREACT:
@@ -230,8 +251,9 @@ def _postact_stage(c_in: int, c_out: int, blocks: int, first_stride: int) -> Lis
 
 
 def config(idx: int, n: Optional[int] = None) -> ModuleSpec:
-    """Benchmark configuration idx in 1..8 (1..5: the CIFAR modules the metric is stated on; 6, 7: the two halves of
-    ResNet-18 at Tiny-ImageNet resolution, channel counts that are powers of two; 8: bottleneck blocks of ResNet-101).  `n` overrides the batch size (for bounded CPU timing and
+    """Benchmark configuration idx in 1..10 (1..5: the CIFAR modules the metric is stated on; 6, 7: the two halves of
+    ResNet-18 at Tiny-ImageNet resolution, channel counts that are powers of two; 8: bottleneck blocks of ResNet-101;
+    9: ResNet-18's lower half with the 7x7 stem and max-pool; 10: inverted residual blocks of MobileNet-v2).  `n` overrides the batch size (for bounded CPU timing and
     small parity cases); everything else keeps its real shape."""
     hyper = dict(momentum=0.9, weight_decay=5e-4, bn_eps=1e-5, bn_momentum=0.1, lr=0.1)
     if idx == 1:
@@ -281,7 +303,20 @@ def config(idx: int, n: Optional[int] = None) -> ModuleSpec:
         ls = [Layer(BOTTLENECK_POSTACT, 1024, 1024, 1) for _ in range(8)]
         return ModuleSpec(n or 128, 1024, 14, 14, ls, delay=1, is_bottom=False, beta=0.5,
                           name="cfg8 ResNet-101 ImageNet K=4 module 2 (8 bottleneck blocks 1024/256 @14x14)", **hyper)
-    raise ValueError("config index must be 1..8")
+    if idx == 9:
+        # ResNet-18 with the ImageNet stem at Tiny-ImageNet resolution, K = 2, module 0: 7x7 convolution stride 2 + BN + ReLU +
+        # 3x3 max-pool stride 2 (64x64 -> 16x16), then blocks 1-4
+        ls = [Layer(STEM_POOL, 3, 64, 4)] + _postact_stage(64, 64, 2, 1) + _postact_stage(64, 128, 2, 2)
+        return ModuleSpec(n or 128, 3, 64, 64, ls, delay=1, is_bottom=True, beta=0.5,
+                          name="cfg9 ResNet-18 (7x7 stem + max-pool) Tiny-ImageNet K=2 module 0", **hyper)
+    if idx == 10:
+        # MobileNet-v2 on Tiny-ImageNet (Table V), a middle module: the 64- and 96-channel stages (inverted residual blocks,
+        # expansion 6), entered from the 32-channel stage at 32x32 through the stride-2 block
+        ls = [Layer(INVERTED_RESIDUAL, 32, 64, 2)] + [Layer(INVERTED_RESIDUAL, 64, 64, 1) for _ in range(3)] \
+            + [Layer(INVERTED_RESIDUAL, 64, 96, 1)] + [Layer(INVERTED_RESIDUAL, 96, 96, 1) for _ in range(2)]
+        return ModuleSpec(n or 128, 32, 32, 32, ls, delay=1, is_bottom=False, beta=0.5,
+                          name="cfg10 MobileNet-v2 Tiny-ImageNet module (7 inverted residual blocks 64/96)", **hyper)
+    raise ValueError("config index must be 1..10")
 
 
 def conv_flops(spec: ModuleSpec) -> int:
@@ -308,6 +343,15 @@ def conv_flops(spec: ModuleSpec) -> int:
                 convs.append((L.c_in, L.c_out, 1, True))
         elif L.kind == STEM:
             convs.append((L.c_in, L.c_out, 9, True))
+        elif L.kind == STEM_POOL:
+            # the 7x7 convolution runs at half the input resolution; the pool halves it again
+            hc, wc = (h - 1) // 2 + 1, (w - 1) // 2 + 1
+            total += (2 if first and spec.is_bottom else 3) * 2 * spec.n * hc * wc * L.c_in * L.c_out * 49
+        elif L.kind == INVERTED_RESIDUAL:
+            f1 = 2 * spec.n * h * w * L.c_in * L.c_mid           # expansion at the input resolution
+            total += (2 if first and spec.is_bottom else 3) * f1
+            total += 3 * 2 * m * L.c_mid * 9                     # depthwise
+            convs.append((L.c_mid, L.c_out, 1, False))
         else:
             convs.append((L.c_in, L.c_out, 9, True))
             convs.append((L.c_out, L.c_out, 9, False))

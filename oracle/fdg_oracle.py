@@ -67,6 +67,12 @@ _SRC = os.path.join(_HERE, "fdg_oracle_kernels.c")
 
 # layer kinds, numerically equal to the C ABI's fdg_layer_kind (an interface constant)
 STEM, BASIC_POSTACT, BASIC_PREACT, HEAD_POSTACT, HEAD_PREACT, BOTTLENECK_POSTACT = 0, 1, 2, 3, 4, 5
+# Layers of the Tiny-ImageNet networks of Table V: the ImageNet stem of ResNet-18 (7x7 convolution stride 2, batch norm,
+# ReLU, 3x3 max-pool stride 2) and the inverted residual block of MobileNet-v2 (1x1 expansion by 6, 3x3 depthwise
+# convolution carrying the stride, 1x1 projection; batch norm after each, ReLU6 after the first two, the input added
+# when stride and channels allow).  The paper names the networks and says they are the usual ones; nothing more.
+STEM_POOL, INVERTED_RESIDUAL = 6, 7
+EXPANSION = 6
 
 
 def lib_path(dtype) -> str:
@@ -174,6 +180,55 @@ class Kernels:
         self.lib.fdgref_relu_bwd(_p(x), _p(dy), _p(dx), ctypes.c_size_t(x.size))
         return dx
 
+    def relu6_fwd(self, x) -> np.ndarray:
+        x = self._a(x)
+        y = np.empty_like(x)
+        self.lib.fdgref_relu6_fwd(_p(x), _p(y), ctypes.c_size_t(x.size))
+        return y
+
+    def relu6_bwd(self, x, dy) -> np.ndarray:
+        x, dy = self._a(x), self._a(dy)
+        dx = np.empty_like(x)
+        self.lib.fdgref_relu6_bwd(_p(x), _p(dy), _p(dx), ctypes.c_size_t(x.size))
+        return dx
+
+    def maxpool_fwd(self, x, k: int, stride: int, pad: int) -> np.ndarray:
+        x = self._a(x)
+        N, C, H, W = x.shape
+        y = np.empty((N, C, (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1), self.dt)
+        self.lib.fdgref_maxpool_fwd(_p(x), _p(y), N, C, H, W, k, stride, pad)
+        return y
+
+    def maxpool_bwd(self, x, dy, k: int, stride: int, pad: int) -> np.ndarray:
+        x, dy = self._a(x), self._a(dy)
+        N, C, H, W = x.shape
+        dx = np.empty_like(x)
+        self.lib.fdgref_maxpool_bwd(_p(x), _p(dy), _p(dx), N, C, H, W, k, stride, pad)
+        return dx
+
+    def dwconv_fwd(self, x, w, stride: int, pad: int) -> np.ndarray:
+        x, w = self._a(x), self._a(w)
+        N, C, H, W = x.shape
+        k = w.shape[-1]
+        assert w.shape == (C, 1, k, k)
+        y = np.empty((N, C, (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1), self.dt)
+        self.lib.fdgref_dwconv2d_fwd(_p(x), _p(w), _p(y), N, C, H, W, k, stride, pad)
+        return y
+
+    def dwconv_bwd_data(self, dy, w, x_shape, stride: int, pad: int) -> np.ndarray:
+        dy, w = self._a(dy), self._a(w)
+        N, C, H, W = x_shape
+        dx = np.empty((N, C, H, W), self.dt)
+        self.lib.fdgref_dwconv2d_bwd_data(_p(dy), _p(w), _p(dx), N, C, H, W, w.shape[-1], stride, pad)
+        return dx
+
+    def dwconv_bwd_weight(self, x, dy, k: int, stride: int, pad: int) -> np.ndarray:
+        x, dy = self._a(x), self._a(dy)
+        N, C, H, W = x.shape
+        dw = np.empty((C, 1, k, k), self.dt)
+        self.lib.fdgref_dwconv2d_bwd_weight(_p(x), _p(dy), _p(dw), N, C, H, W, k, stride, pad)
+        return dw
+
     def avgpool_fwd(self, x) -> np.ndarray:
         x = self._a(x)
         N, C, H, W = x.shape
@@ -255,6 +310,13 @@ def oracle_param_layout(spec) -> List[Tuple[str, Tuple[int, ...]]]:
             out += bn("bn2", L.c_out) + [(f"{i}.conv2.w", (L.c_out, L.c_out, 3, 3))]
             if _projects(L):
                 out += [(f"{i}.proj.w", (L.c_out, L.c_in, 1, 1))]
+        elif L.kind == STEM_POOL:
+            out += [(f"{i}.conv.w", (L.c_out, L.c_in, 7, 7))] + bn("bn", L.c_out)
+        elif L.kind == INVERTED_RESIDUAL:
+            cm = EXPANSION * L.c_in
+            out += [(f"{i}.conv1.w", (cm, L.c_in, 1, 1))] + bn("bn1", cm)
+            out += [(f"{i}.conv2.w", (cm, 1, 3, 3))] + bn("bn2", cm)
+            out += [(f"{i}.conv3.w", (L.c_out, cm, 1, 1))] + bn("bn3", L.c_out)
         elif L.kind == HEAD_POSTACT:
             out += [(f"{i}.fc.w", (J, L.c_in)), (f"{i}.fc.b", (J,))]
         elif L.kind == HEAD_PREACT:
@@ -456,6 +518,21 @@ class OracleModule:
                     sc = z
                 t.update(a1=a1, a2=a2)
                 z = k.relu_fwd(b3 + sc)
+            elif L.kind == STEM_POOL:
+                assert L.stride == 4, "a 7x7 convolution of stride 2 followed by a pool of stride 2"
+                c = q(k.conv_fwd(zb, th[f"{i}.conv.w"], 2, 3))
+                a = q(k.relu_fwd(self._bn(f"{i}.bn", c, th, t)))
+                t.update(a=a)
+                z = k.maxpool_fwd(a, 3, 2, 1)
+            elif L.kind == INVERTED_RESIDUAL:
+                c1 = q(k.conv_fwd(zb, th[f"{i}.conv1.w"], 1, 0))
+                a1 = q(k.relu6_fwd(self._bn(f"{i}.bn1", c1, th, t)))
+                c2 = q(k.dwconv_fwd(a1, th[f"{i}.conv2.w"], L.stride, 1))
+                a2 = q(k.relu6_fwd(self._bn(f"{i}.bn2", c2, th, t)))
+                c3 = q(k.conv_fwd(a2, th[f"{i}.conv3.w"], 1, 0))
+                b3 = self._bn(f"{i}.bn3", c3, th, t)
+                t.update(a1=a1, a2=a2)
+                z = b3 + z if (L.stride == 1 and L.c_in == L.c_out) else b3
             elif L.kind == BASIC_PREACT:
                 o1 = q(k.relu_fwd(self._bn(f"{i}.bn1", zb, th, t)))
                 c1 = q(k.conv_fwd(o1, th[f"{i}.conv1.w"], L.stride, 1))
@@ -573,6 +650,25 @@ class OracleModule:
                 else:
                     dx = dx + ds
                 dz = dx
+            else:
+                dz = None
+        elif L.kind == STEM_POOL:
+            da = k.maxpool_bwd(t["a"], dz, 3, 2, 1)
+            dc = q(self._bn_back(f"{i}.bn", k.relu_bwd(t["a"], da), th, t, g))
+            g[f"{i}.conv.w"][...] = k.conv_bwd_weight(x, dc, 7, 2, 3)
+            dz = k.conv_bwd_data(dc, th[f"{i}.conv.w"], x.shape, 2, 3) if need_dx else None
+        elif L.kind == INVERTED_RESIDUAL:
+            dc3 = q(self._bn_back(f"{i}.bn3", dz, th, t, g))        # no gate: the block ends in a batch norm
+            g[f"{i}.conv3.w"][...] = k.conv_bwd_weight(t["a2"], dc3, 1, 1, 0)
+            da2 = q(k.conv_bwd_data(dc3, th[f"{i}.conv3.w"], t["a2"].shape, 1, 0))
+            dc2 = q(self._bn_back(f"{i}.bn2", k.relu6_bwd(t["a2"], da2), th, t, g))
+            g[f"{i}.conv2.w"][...] = k.dwconv_bwd_weight(t["a1"], dc2, 3, L.stride, 1)
+            da1 = q(k.dwconv_bwd_data(dc2, th[f"{i}.conv2.w"], t["a1"].shape, L.stride, 1))
+            dc1 = q(self._bn_back(f"{i}.bn1", k.relu6_bwd(t["a1"], da1), th, t, g))
+            g[f"{i}.conv1.w"][...] = k.conv_bwd_weight(x, dc1, 1, 1, 0)
+            if need_dx:
+                dx = k.conv_bwd_data(dc1, th[f"{i}.conv1.w"], x.shape, 1, 0)
+                dz = dx + dz if (L.stride == 1 and L.c_in == L.c_out) else dx
             else:
                 dz = None
         elif L.kind == BASIC_PREACT:

@@ -195,6 +195,136 @@ void fdgref_relu_bwd(const real* x, const real* dy, real* dx, size_t count) {
   for (size_t i = 0; i < count; ++i) dx[i] = x[i] > 0 ? dy[i] : 0;
 }
 
+/* ---- layers of the Tiny-ImageNet networks of Table V (ResNet-18's ImageNet stem, MobileNet-v2's blocks) ---- */
+
+/* y = min(max(x, 0), 6) */
+void fdgref_relu6_fwd(const real* x, real* y, size_t count) {
+#pragma omp parallel for schedule(static)
+  for (size_t i = 0; i < count; ++i) y[i] = x[i] > 0 ? (x[i] < 6 ? x[i] : 6) : 0;
+}
+
+/* dx = dy where 0 < x < 6, else 0 (derivative taken as 0 at both corners).  x may be the layer's input or its
+ * clamped output: the two are equal exactly where the test holds. */
+void fdgref_relu6_bwd(const real* x, const real* dy, real* dx, size_t count) {
+#pragma omp parallel for schedule(static)
+  for (size_t i = 0; i < count; ++i) dx[i] = (x[i] > 0 && x[i] < 6) ? dy[i] : 0;
+}
+
+/* Max-pool k x k, stride s, padding p (padding never wins: windows are clipped to the image):
+ *   y[n,c,ho,wo] = max over the window of x.  Among equal maxima the FIRST in scan order (rows, then columns) is the
+ *   one the gradient goes to. */
+void fdgref_maxpool_fwd(const real* x, real* y, int N, int C, int H, int W, int k, int s, int p) {
+  const int Ho = out_size(H, k, s, p), Wo = out_size(W, k, s, p);
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < N; ++n)
+    for (int c = 0; c < C; ++c) {
+      const real* xp = x + IDX4(n, c, 0, 0, C, H, W);
+      real* yp = y + IDX4(n, c, 0, 0, C, Ho, Wo);
+      for (int ho = 0; ho < Ho; ++ho)
+        for (int wo = 0; wo < Wo; ++wo) {
+          int have = 0;
+          real best = 0;
+          for (int r = 0; r < k; ++r)
+            for (int q = 0; q < k; ++q) {
+              const int h = ho * s + r - p, w = wo * s + q - p;
+              if (h < 0 || h >= H || w < 0 || w >= W) continue;
+              if (!have || xp[h * W + w] > best) { best = xp[h * W + w]; have = 1; }
+            }
+          yp[ho * Wo + wo] = best;
+        }
+    }
+}
+
+/* dx[n,c,h,w] = sum of dy over the windows whose (first) maximum sits at (h,w) */
+void fdgref_maxpool_bwd(const real* x, const real* dy, real* dx, int N, int C, int H, int W, int k, int s, int p) {
+  const int Ho = out_size(H, k, s, p), Wo = out_size(W, k, s, p);
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < N; ++n)
+    for (int c = 0; c < C; ++c) {
+      const real* xp = x + IDX4(n, c, 0, 0, C, H, W);
+      const real* dyp = dy + IDX4(n, c, 0, 0, C, Ho, Wo);
+      real* dxp = dx + IDX4(n, c, 0, 0, C, H, W);
+      for (int i = 0; i < H * W; ++i) dxp[i] = 0;
+      for (int ho = 0; ho < Ho; ++ho)
+        for (int wo = 0; wo < Wo; ++wo) {
+          int at = -1;
+          real best = 0;
+          for (int r = 0; r < k; ++r)
+            for (int q = 0; q < k; ++q) {
+              const int h = ho * s + r - p, w = wo * s + q - p;
+              if (h < 0 || h >= H || w < 0 || w >= W) continue;
+              if (at < 0 || xp[h * W + w] > best) { best = xp[h * W + w]; at = h * W + w; }
+            }
+          if (at >= 0) dxp[at] += dyp[ho * Wo + wo];
+        }
+    }
+}
+
+/* Depthwise convolution (one k x k filter per channel, w[c,r,q]):
+ *   y[n,c,ho,wo] = sum_{r,q} x[n,c,ho*s+r-p,wo*s+q-p] * w[c,r,q] */
+void fdgref_dwconv2d_fwd(const real* x, const real* w, real* y, int N, int C, int H, int W, int k, int s, int p) {
+  const int Ho = out_size(H, k, s, p), Wo = out_size(W, k, s, p);
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < N; ++n)
+    for (int c = 0; c < C; ++c) {
+      const real* xp = x + IDX4(n, c, 0, 0, C, H, W);
+      real* yp = y + IDX4(n, c, 0, 0, C, Ho, Wo);
+      for (int ho = 0; ho < Ho; ++ho)
+        for (int wo = 0; wo < Wo; ++wo) {
+          double acc = 0.0;
+          for (int r = 0; r < k; ++r)
+            for (int q = 0; q < k; ++q) {
+              const int h = ho * s + r - p, ww = wo * s + q - p;
+              if (h < 0 || h >= H || ww < 0 || ww >= W) continue;
+              acc += (double)xp[h * W + ww] * (double)w[((size_t)c * k + r) * k + q];
+            }
+          yp[ho * Wo + wo] = (real)acc;
+        }
+    }
+}
+
+/* dx[n,c,h,w] = sum_{r,q : h=ho*s+r-p, w=wo*s+q-p} dy[n,c,ho,wo] * w[c,r,q] */
+void fdgref_dwconv2d_bwd_data(const real* dy, const real* w, real* dx, int N, int C, int H, int W, int k, int s, int p) {
+  const int Ho = out_size(H, k, s, p), Wo = out_size(W, k, s, p);
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < N; ++n)
+    for (int c = 0; c < C; ++c) {
+      const real* dyp = dy + IDX4(n, c, 0, 0, C, Ho, Wo);
+      real* dxp = dx + IDX4(n, c, 0, 0, C, H, W);
+      for (int i = 0; i < H * W; ++i) dxp[i] = 0;
+      for (int ho = 0; ho < Ho; ++ho)
+        for (int wo = 0; wo < Wo; ++wo)
+          for (int r = 0; r < k; ++r)
+            for (int q = 0; q < k; ++q) {
+              const int h = ho * s + r - p, ww = wo * s + q - p;
+              if (h < 0 || h >= H || ww < 0 || ww >= W) continue;
+              dxp[h * W + ww] += dyp[ho * Wo + wo] * w[((size_t)c * k + r) * k + q];
+            }
+    }
+}
+
+/* dw[c,r,q] = sum_{n,ho,wo} dy[n,c,ho,wo] * x[n,c,ho*s+r-p,wo*s+q-p] */
+void fdgref_dwconv2d_bwd_weight(const real* x, const real* dy, real* dw, int N, int C, int H, int W, int k, int s, int p) {
+  const int Ho = out_size(H, k, s, p), Wo = out_size(W, k, s, p);
+#pragma omp parallel for schedule(static)
+  for (int c = 0; c < C; ++c)
+    for (int r = 0; r < k; ++r)
+      for (int q = 0; q < k; ++q) {
+        double acc = 0.0;
+        for (int n = 0; n < N; ++n) {
+          const real* xp = x + IDX4(n, c, 0, 0, C, H, W);
+          const real* dyp = dy + IDX4(n, c, 0, 0, C, Ho, Wo);
+          for (int ho = 0; ho < Ho; ++ho)
+            for (int wo = 0; wo < Wo; ++wo) {
+              const int h = ho * s + r - p, ww = wo * s + q - p;
+              if (h < 0 || h >= H || ww < 0 || ww >= W) continue;
+              acc += (double)dyp[ho * Wo + wo] * (double)xp[h * W + ww];
+            }
+        }
+        dw[((size_t)c * k + r) * k + q] = (real)acc;
+      }
+}
+
 /* p[n,c] = average over (h,w) of x[n,c,h,w] */
 void fdgref_avgpool_fwd(const real* x, real* p, int N, int C, int H, int W) {
   const int HW = H * W;

@@ -226,3 +226,71 @@ def test_float32_build_matches_float64_build():
     np.testing.assert_allclose(K32.conv_bwd_data(g, w, x.shape, 1, 1), K64.conv_bwd_data(g, w, x.shape, 1, 1), rtol=1e-4, atol=1e-5)
     y32, y64 = K32.bn_fwd(x, np.ones(8), np.zeros(8), 1e-5)[0], K64.bn_fwd(x, np.ones(8), np.zeros(8), 1e-5)[0]
     np.testing.assert_allclose(y32, y64, rtol=1e-4, atol=1e-5)
+
+
+# ---- layers of the Tiny-ImageNet networks (Table V): max-pool, depthwise convolution, ReLU6 -------------------------
+@pytest.mark.parametrize("shape,k,s,p", [((2, 3, 7, 9), 3, 2, 1), ((1, 2, 8, 8), 3, 2, 1), ((2, 1, 5, 5), 2, 2, 0), ((1, 2, 6, 7), 3, 1, 1)])
+def test_maxpool_brute_force_ties_and_torch(shape, k, s, p):
+    rng = np.random.default_rng(sum(shape) + k)
+    # few distinct values: windows with several equal maxima are the rule, so the tie rule is what is tested
+    x = rng.integers(0, 4, shape).astype(np.float64)
+    y = K64.maxpool_fwd(x, k, s, p)
+    N, C, H, W = shape
+    Ho, Wo = y.shape[2:]
+    dy = rng.standard_normal(y.shape)
+    want_y = np.full(y.shape, -np.inf)
+    want_dx = np.zeros(shape)
+    for n, c, ho, wo in itertools.product(range(N), range(C), range(Ho), range(Wo)):
+        cells = [(ho * s + r - p, wo * s + q - p) for r in range(k) for q in range(k)]
+        cells = [(h, w) for h, w in cells if 0 <= h < H and 0 <= w < W]
+        vals = [x[n, c, h, w] for h, w in cells]
+        m = max(vals)
+        want_y[n, c, ho, wo] = m
+        h, w = cells[vals.index(m)]          # the first one in scan order
+        want_dx[n, c, h, w] += dy[n, c, ho, wo]
+    np.testing.assert_array_equal(y, want_y)
+    dx = K64.maxpool_bwd(x, dy, k, s, p)
+    np.testing.assert_allclose(dx, want_dx, rtol=0, atol=1e-14)
+    assert math.isclose(dx.sum(), dy.sum(), rel_tol=1e-12)      # every window hands its gradient to exactly one cell
+    xt = torch.tensor(x, requires_grad=True)
+    yt = F.max_pool2d(xt, k, stride=s, padding=p)
+    np.testing.assert_array_equal(yt.detach().numpy(), y)
+    # on inputs without ties torch's gradient is the same map
+    x2 = rng.standard_normal(shape)
+    xt = torch.tensor(x2, requires_grad=True)
+    F.max_pool2d(xt, k, stride=s, padding=p).backward(torch.tensor(dy))
+    np.testing.assert_allclose(K64.maxpool_bwd(x2, dy, k, s, p), xt.grad.numpy(), rtol=0, atol=1e-14)
+
+
+@pytest.mark.parametrize("shape,s", [((2, 5, 7, 6), 1), ((2, 4, 8, 9), 2), ((1, 3, 5, 5), 2)])
+def test_depthwise_convolution_is_a_convolution_per_channel(shape, s):
+    rng = np.random.default_rng(11 + s)
+    N, C, H, W = shape
+    x, w = rng.standard_normal(shape), rng.standard_normal((C, 1, 3, 3))
+    y = K64.dwconv_fwd(x, w, s, 1)
+    # one ordinary single-channel convolution per channel (the dense routine is pinned above)
+    for c in range(C):
+        np.testing.assert_allclose(y[:, c:c + 1], K64.conv_fwd(x[:, c:c + 1], w[c:c + 1], s, 1), rtol=1e-13, atol=1e-13)
+    dy = rng.standard_normal(y.shape)
+    dx, dw = K64.dwconv_bwd_data(dy, w, shape, s, 1), K64.dwconv_bwd_weight(x, dy, 3, s, 1)
+    # adjoint identities: <dy, conv(x, w)> = <dx, x> = <dw, w>
+    assert math.isclose(float((dy * y).sum()), float((dx * x).sum()), rel_tol=1e-11)
+    assert math.isclose(float((dy * y).sum()), float((dw * w).sum()), rel_tol=1e-11)
+    xt, wt = torch.tensor(x, requires_grad=True), torch.tensor(w, requires_grad=True)
+    yt = F.conv2d(xt, wt, stride=s, padding=1, groups=C)
+    np.testing.assert_allclose(y, yt.detach().numpy(), rtol=1e-12, atol=1e-12)
+    yt.backward(torch.tensor(dy))
+    np.testing.assert_allclose(dx, xt.grad.numpy(), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(dw, wt.grad.numpy(), rtol=1e-12, atol=1e-12)
+
+
+def test_relu6():
+    x = np.array([-1.0, 0.0, 1e-9, 3.0, 6.0 - 1e-9, 6.0, 7.5])
+    np.testing.assert_array_equal(K64.relu6_fwd(x), np.array([0.0, 0.0, 1e-9, 3.0, 6.0 - 1e-9, 6.0, 6.0]))
+    dy = np.arange(1.0, 8.0)
+    want = np.array([0.0, 0.0, 3.0, 4.0, 5.0, 0.0, 0.0])
+    np.testing.assert_array_equal(K64.relu6_bwd(x, dy), want)
+    np.testing.assert_array_equal(K64.relu6_bwd(K64.relu6_fwd(x), dy), want)     # gated on the clamped output: the same map
+    xt = torch.tensor(x, requires_grad=True)
+    F.relu6(xt).backward(torch.tensor(dy))
+    np.testing.assert_array_equal(xt.grad.numpy(), want)

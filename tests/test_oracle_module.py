@@ -34,6 +34,13 @@ TINY = {
     "bottleneck_project": ModuleSpec(2, 4, 6, 6, [Layer(W.BOTTLENECK_POSTACT, 4, 8, 2)]),
     "bottleneck_stack_head": ModuleSpec(3, 4, 6, 6, [Layer(W.BOTTLENECK_POSTACT, 4, 8, 1), Layer(W.BOTTLENECK_POSTACT, 8, 8, 2),
                                                     Layer(W.HEAD_POSTACT, 8)], num_classes=5),
+    "stem_pool": ModuleSpec(2, 3, 13, 14, [Layer(W.STEM_POOL, 3, 4, 4)], is_bottom=False),
+    "stem_pool_stack_head": ModuleSpec(3, 3, 16, 16, [Layer(W.STEM_POOL, 3, 8, 4), Layer(W.BASIC_POSTACT, 8, 8, 1), Layer(W.HEAD_POSTACT, 8)],
+                                       num_classes=5),
+    "inverted_residual_identity": ModuleSpec(2, 4, 5, 5, [Layer(W.INVERTED_RESIDUAL, 4, 4, 1)]),
+    "inverted_residual_stride2": ModuleSpec(2, 4, 6, 7, [Layer(W.INVERTED_RESIDUAL, 4, 8, 2)]),
+    "inverted_residual_stack": ModuleSpec(2, 4, 6, 6, [Layer(W.INVERTED_RESIDUAL, 4, 8, 1), Layer(W.INVERTED_RESIDUAL, 8, 8, 1),
+                                                     Layer(W.INVERTED_RESIDUAL, 8, 8, 2)]),
     "stack": ModuleSpec(2, 3, 8, 8, [Layer(W.STEM, 3, 4, 1), Layer(W.BASIC_POSTACT, 4, 4, 1),
                                     Layer(W.BASIC_POSTACT, 4, 8, 2), Layer(W.BASIC_POSTACT, 8, 8, 1)]),
 }

@@ -5,6 +5,7 @@ import torch
 import torch.nn.functional as F
 
 STEM, BASIC_POSTACT, BASIC_PREACT, HEAD_POSTACT, HEAD_PREACT, BOTTLENECK_POSTACT = 0, 1, 2, 3, 4, 5
+STEM_POOL, INVERTED_RESIDUAL = 6, 7
 
 
 def _bn(x, g, b, eps):
@@ -54,6 +55,15 @@ def forward(spec, params, x, labels=None):
             else:
                 sc = z
             z = F.relu(r + sc)
+        elif L.kind == STEM_POOL:
+            w, g, b = next(it), next(it), next(it)
+            z = F.max_pool2d(F.relu(_bn(F.conv2d(z, w, stride=2, padding=3), g, b, eps)), 3, stride=2, padding=1)
+        elif L.kind == INVERTED_RESIDUAL:
+            w1, g1, b1, w2, g2, b2, w3, g3, b3 = (next(it) for _ in range(9))
+            a = F.relu6(_bn(F.conv2d(z, w1), g1, b1, eps))
+            a = F.relu6(_bn(F.conv2d(a, w2, stride=L.stride, padding=1, groups=a.shape[1]), g2, b2, eps))
+            r = _bn(F.conv2d(a, w3), g3, b3, eps)
+            z = r + z if (L.stride == 1 and L.c_in == L.c_out) else r
         elif L.kind == BASIC_PREACT:
             g1, b1, w1, g2, b2, w2 = (next(it) for _ in range(6))
             o1 = F.relu(_bn(z, g1, b1, eps))
