@@ -55,7 +55,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..8 (default 4: WRN-28-10 top module)")
+    ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..10 (default 4: WRN-28-10 top module)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--two-streams", action="store_true",
                     help="forward on one stream, delayed backward + update on another (modules with delay >= 1: the two touch "
@@ -85,7 +85,7 @@ def cpu_baseline(idx: int, sample_batch: int):
     import numpy as np
     import fdg_workloads as W
     from oracle import fdg_oracle
-    n = sample_batch or {1: 128, 2: 128, 3: 128, 4: 128, 5: 32, 6: 64, 7: 32, 8: 32}[idx]   # about 10-30 s of oracle time
+    n = sample_batch or {1: 128, 2: 128, 3: 128, 4: 128, 5: 32, 6: 64, 7: 32, 8: 32, 9: 32, 10: 64}[idx]   # about 10-30 s of oracle time
     spec = W.config(idx, n=n)
     spec.delay = 0
     m = fdg_oracle.OracleModule(spec, np.float32, storage="fp32")

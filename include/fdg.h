@@ -72,6 +72,14 @@ typedef enum {
  *   BOTTLENECK_POSTACT: conv1x1(c_in->c_out/4) -> BN -> ReLU -> conv3x3(c_out/4->c_out/4, stride) -> BN -> ReLU ->
  *                       conv1x1(c_out/4->c_out) -> BN -> (+shortcut) -> ReLU, shortcut as in BASIC_POSTACT; the
  *                       block of ResNet-101 (Section V-C, Table VII); c_out must be a multiple of 32
+ *   STEM_POOL         : conv7x7(c_in->c_out, stride 2, padding 3) -> BN -> ReLU -> max-pool 3x3 (stride 2, padding 1): the
+ *                       ImageNet stem of ResNet-18 / ResNet-101 (Table V, Table VII).  `stride` must be 4 (the two halvings);
+ *                       c_in <= 8; only as the first layer of a bottom module (it has no input gradient: it is the first
+ *                       layer of its network), else FDG_ERR_UNSUPPORTED.  Parameters: conv.w [c_out, c_in, 7, 7], gamma, beta
+ *   INVERTED_RESIDUAL : conv1x1(c_in->6 c_in) -> BN -> ReLU6 -> depthwise conv3x3(stride) -> BN -> ReLU6 ->
+ *                       conv1x1(6 c_in->c_out) -> BN, plus the input when stride == 1 and c_in == c_out: the block of
+ *                       MobileNet-v2 (Table V) with its expansion factor 6.  Parameters: conv1.w [6 c_in, c_in, 1, 1], bn1,
+ *                       conv2.w [6 c_in, 1, 3, 3], bn2, conv3.w [c_out, 6 c_in, 1, 1], bn3 (gamma, beta each)
  * A head, if present, must be the last layer; the module is then a TOP module (Section III-B:
  * its gradient is not shrunk and it needs no gradient from above).                              */
 typedef enum {
@@ -80,14 +88,16 @@ typedef enum {
   FDG_BASIC_PREACT = 2,
   FDG_HEAD_POSTACT = 3,
   FDG_HEAD_PREACT = 4,
-  FDG_BOTTLENECK_POSTACT = 5
+  FDG_BOTTLENECK_POSTACT = 5,
+  FDG_STEM_POOL = 6,
+  FDG_INVERTED_RESIDUAL = 7
 } fdg_layer_kind;
 
 typedef struct {
   int32_t kind;   /* fdg_layer_kind */
   int32_t c_in;   /* input channels; must equal the previous layer's c_out */
   int32_t c_out;  /* output channels (heads: ignored, num_classes is used) */
-  int32_t stride; /* 1 or 2 (heads: ignored) */
+  int32_t stride; /* 1 or 2 (heads: ignored; STEM_POOL: 4) */
 } fdg_layer_desc;
 
 typedef struct {
@@ -230,6 +240,8 @@ fdg_status fdg_queue_state(const fdg_module* m, int32_t* outstanding, int64_t* o
  *        BOTTLENECK_POSTACT 0 = conv1 output, 1 = relu(bn1), 2 = conv2 output, 3 = projection output, 4 = relu(bn2),
  *                           5 = conv3 output
  *        HEAD_PREACT        0 = relu(bn(x))
+ *        STEM_POOL          0 = conv output, 1 = relu(bn) (the pool's input), both at half the input resolution
+ *        INVERTED_RESIDUAL  0 = conv1 output, 1 = relu6(bn1), 2 = depthwise output, 4 = relu6(bn2), 5 = conv3 output
  *   which 6    : the bf16 copy of the layer's output (the next layer's operand and ReLU gate); not for heads
  *   which 7    : the bf16 copy of the layer's input
  *   which 8    : heads: the pooled features [n, c, 1, 1] (fp32)

@@ -153,6 +153,28 @@ int fdgk_pool_bwd(const float* dpooled, float* g_f32, void* g_b16, int n, int hw
 int fdgk_nchw_to_nhwc(const float* src, float* dst_f32, void* dst_b16, int n, int c, int hw, int cp, float scale, void* hip_stream);
 int fdgk_nhwc_to_nchw(const float* src, float* dst, int n, int c, int hw, int cp, void* hip_stream);
 
+/* ---- layers of the Tiny-ImageNet networks of Table V (ResNet-18's ImageNet stem, MobileNet-v2's depthwise convolution) ----
+ * All tensors NHWC bf16 unless marked, c % 8 == 0.
+ * fdgk_im2col7:       col[m, kh, kw, cc] = x8[n, 2 oh - 3 + kh, 2 ow - 3 + kw, cc] for kh < 7, kw < 7 inside the image, else 0
+ *                     (m = (n, oh, ow) over the output grid ((h-1)/2+1) x ((w-1)/2+1); kw runs to 8, cc over the 8 stored input
+ *                     channels): the 448 operand elements of output pixel m of a 7x7 convolution with stride 2 and padding 3,
+ *                     which is then fdgk_conv_fwd / fdgk_conv_wgrad with ksize 1 and ci = 448 on col.
+ * fdgk_maxpool3s2:    y[n, ho, wo, c] = max over the 3x3 window at stride 2, padding 1 (windows clipped to the image), into
+ *                     y_f32 and / or y_b16.
+ * fdgk_maxpool3s2_bwd: dx_f32[n, h, w, c] = sum of dy_f32 over the windows whose first maximum in scan order (rows, then
+ *                     columns) is (h, w); x_b16 is the pool's input.
+ * fdgk_dwconv3_*:     depthwise 3x3 convolution, padding 1, stride 1 or 2; wt_b16 = [9][c] (tap-major), dw_f32 = [c][9];
+ *                     the weight gradient takes scratch of fdgk_dwconv3_wgrad_scratch_bytes and adds its parts in a fixed
+ *                     order (same bits every run).                                                                         */
+int fdgk_im2col7(const void* x8_b16, void* col_b16, int n, int h, int w, void* hip_stream);
+int fdgk_maxpool3s2(const void* x_b16, float* y_f32, void* y_b16, int n, int h, int w, int c, void* hip_stream);
+int fdgk_maxpool3s2_bwd(const void* x_b16, const float* dy_f32, float* dx_f32, int n, int h, int w, int c, void* hip_stream);
+int fdgk_dwconv3_fwd(const void* x_b16, const void* wt_b16, void* y_b16, int n, int h, int w, int c, int stride, void* hip_stream);
+int fdgk_dwconv3_dgrad(const void* dy_b16, const void* wt_b16, void* dx_b16, int n, int h, int w, int c, int stride, void* hip_stream);
+size_t fdgk_dwconv3_wgrad_scratch_bytes(int n, int h, int w, int c, int stride);
+int fdgk_dwconv3_wgrad(const void* x_b16, const void* dy_b16, float* dw_f32, float* scratch_f32, size_t scratch_bytes, int n, int h,
+                       int w, int c, int stride, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

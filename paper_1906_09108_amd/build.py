@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfdg.so")
-SOURCES = ["conv_kernels.hip", "conv_wide_kernels.hip", "conv_narrow_kernels.hip", "stream_kernels.hip", "fdg_module.hip", "fdg_chain.hip", "kernel_api.hip"]
+SOURCES = ["conv_kernels.hip", "conv_wide_kernels.hip", "conv_narrow_kernels.hip", "stream_kernels.hip", "layer_kernels.hip", "fdg_module.hip", "fdg_chain.hip", "kernel_api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

@@ -183,7 +183,7 @@ struct BnApplyArgs {
   float* run_var2;
   int M, C;
   float eps, momentum;
-  int relu;
+  int relu;              // 0: none, 1: max(y, 0), 2: min(max(y, 0), 6)
   int rep_stride;        // stat_t elements between the copies of sums and of sums2 (0: one copy)
 };
 hipError_t launch_bn_apply(const BnApplyArgs& a, hipStream_t s);
@@ -204,7 +204,8 @@ struct BnBwdArgs {
   float* dbeta;          // [C]
   int M, C;
   float eps;
-  int dy_gated;          // apply only: dy is already zero where the gate is closed (mask is not read)
+  float gate_hi;         // > 0: the gate is also closed where mask >= gate_hi (ReLU6: 6); 0: open above
+  int dy_gated;          // dy needs no gate: it is already zero where the gate is closed, or there is none (mask is not read)
   int raw_sums;          // apply only: bsums holds sum g and sum g*x (not g*xhat), as a gated data gradient leaves them
   int rep_stride;        // stat_t elements between the copies of sums (0: one copy)
   int brep_stride;       // apply only: stat_t elements between the copies of bsums (0: one copy); the reduce pass adds into copy 0
@@ -252,6 +253,21 @@ hipError_t launch_emit_weights(const float* params, bf16_t* warena, const Weight
 hipError_t launch_sgd_emit(float* params, float* mom, const float* grads, bf16_t* warena, float* small_snap,
                            const WeightEmitEntry* table_dev, int nconv, int conv_blocks, size_t small_off, size_t small_count,
                            float lr, float mu, float wd, hipStream_t s);
+
+// ---- layers of the Tiny-ImageNet networks (layer_kernels.hip) ----
+// col[m, kh, kw8, c8] of a 7x7 stride-2 padding-3 convolution over x8 [N, H, W, 8]: 448 bf16 per output pixel m = (n, oh, ow),
+// the column kw = 7 and everything outside the image zero
+hipError_t launch_im2col7(const bf16_t* x8, bf16_t* col, int N, int H, int W, hipStream_t s);
+// 3x3 max-pool, stride 2, padding 1 over x [N, H, W, C] (C % 8 == 0); backward: dy fp32 [N, Ho, Wo, C] to the first maximum
+// of each window in scan order, dx fp32 [N, H, W, C] written everywhere
+hipError_t launch_maxpool3s2(const bf16_t* x, float* y_f32, bf16_t* y_b16, int N, int H, int W, int C, hipStream_t s);
+hipError_t launch_maxpool3s2_bwd(const bf16_t* x, const float* dy, float* dx, int N, int H, int W, int C, hipStream_t s);
+// depthwise 3x3 convolution, padding 1, stride 1 or 2; wt bf16 [9][C] (tap-major), dw fp32 [C][9]
+hipError_t launch_dwconv3_fwd(const bf16_t* x, const bf16_t* wt, bf16_t* y, int N, int H, int W, int C, int stride, hipStream_t s);
+hipError_t launch_dwconv3_dgrad(const bf16_t* dy, const bf16_t* wt, bf16_t* dx, int N, int H, int W, int C, int stride, hipStream_t s);
+size_t dwconv3_wgrad_scratch_bytes(int N, int H, int W, int C, int stride);
+hipError_t launch_dwconv3_wgrad(const bf16_t* x, const bf16_t* dy, float* dw, float* scratch, size_t scratch_bytes, int N, int H, int W,
+                                int C, int stride, hipStream_t s);
 
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);  // bytes % 16 == 0
 

@@ -24,6 +24,9 @@ struct ConvInfo {
   ConvShape sh;
   size_t p_off;                // fp32 master [Co][T][Ci] in the parameter arena (elements)
   size_t w_off, wt_off;        // bf16 copies in a slot's weight arena (elements)
+  int stem7_ci = 0;            // > 0: the 7x7 stride-2 stem over stem7_ci channels, held as a 1x1 convolution over the
+                               // 448 = 7 x 8 x 8 (row, column, stored channel) elements that launch_im2col7 lays out per pixel
+  bool depthwise = false;      // sh = {Co = C, Ci = 1, T = 9}: one 3x3 filter per channel, run by the dwconv3 kernels
 };
 struct BnInfo {
   int C, M;
@@ -31,7 +34,7 @@ struct BnInfo {
   size_t stat_off;             // offset of this BN's [2C] block in every per-BN fp32 array
 };
 struct ParamTensor {           // one tensor of the external flat order
-  size_t ext_off, int_off, count;
+  size_t ext_off, int_off, count;   // count: elements of the external tensor
   int conv;                    // index into convs, or -1 (stored as is)
 };
 struct LayerPlan {
@@ -78,6 +81,8 @@ struct Plan {
   size_t o_inter = 0, inter_bytes = 0;
   size_t o_S[2] = {0, 0}, o_G[2] = {0, 0}, o_GB[2] = {0, 0}, o_T[2] = {0, 0}, o_TP = 0, o_TPB = 0, o_dp = 0;
   size_t o_wscratch = 0, wscratch_bytes = 0;   // partial sums of the split weight gradient
+  size_t o_dwscratch = 0, dwscratch_bytes = 0; // the same for depthwise convolutions (they run on the caller's stream)
+  size_t o_col = 0, o_colb = 0, col_bytes = 0; // operand rows of a 7x7 stem (launch_im2col7): the forward's and the backward's copy
   size_t total = 0;
   // layout of a caller-provided trace buffer (parity accessors): per layer the fp32 output of the forward and the fp32
   // input gradient of the backward, [L.size()] = the gradient that entered the module, all NHWC as the kernels leave them
@@ -158,14 +163,19 @@ bool build_plan(const fdg_module_desc* desc, int save_mode, Plan& p, fdg_status*
       break;
     }
     if (ld.kind != FDG_STEM_CONV_BN_RELU && ld.kind != FDG_BASIC_POSTACT && ld.kind != FDG_BASIC_PREACT &&
-        ld.kind != FDG_BOTTLENECK_POSTACT) return false;
+        ld.kind != FDG_BOTTLENECK_POSTACT && ld.kind != FDG_STEM_POOL && ld.kind != FDG_INVERTED_RESIDUAL) return false;
     if (ld.kind == FDG_BOTTLENECK_POSTACT && ld.c_out % 32 != 0) { *why = FDG_ERR_UNSUPPORTED; return false; }
-    if (ld.c_out <= 0 || (ld.stride != 1 && ld.stride != 2)) return false;
+    if (ld.kind == FDG_STEM_POOL) {
+      if (ld.stride != 4 || ld.c_out <= 0) return false;
+      if (i != 0 || !desc->is_bottom || c > 8) { *why = FDG_ERR_UNSUPPORTED; return false; }
+    } else if (ld.c_out <= 0 || (ld.stride != 1 && ld.stride != 2)) return false;
     if (ld.c_out % 8 != 0 || ld.c_out > 2048) { *why = FDG_ERR_UNSUPPORTED; return false; }
-    if (ld.kind != FDG_STEM_CONV_BN_RELU && (c % 8 != 0 || c > 2048)) { *why = FDG_ERR_UNSUPPORTED; return false; }
+    if (ld.kind != FDG_STEM_CONV_BN_RELU && ld.kind != FDG_STEM_POOL && (c % 8 != 0 || c > 2048)) { *why = FDG_ERR_UNSUPPORTED; return false; }
+    if (ld.kind == FDG_INVERTED_RESIDUAL && 6 * c > 2048) { *why = FDG_ERR_UNSUPPORTED; return false; }
     const int ho = (h - 1) / ld.stride + 1, wo = (w - 1) / ld.stride + 1;
     lp.Hi = h; lp.Wi = w; lp.Ho = ho; lp.Wo = wo;
-    lp.projects = ld.kind != FDG_STEM_CONV_BN_RELU && (ld.stride != 1 || ld.c_in != ld.c_out);   // blocks only
+    lp.projects = (ld.kind == FDG_BASIC_POSTACT || ld.kind == FDG_BASIC_PREACT || ld.kind == FDG_BOTTLENECK_POSTACT) &&
+                  (ld.stride != 1 || ld.c_in != ld.c_out);   // blocks with a shortcut only
     const size_t Ein = (size_t)N * h * w * round8(c), Eout = (size_t)N * ho * wo * ld.c_out;
     if (ld.kind == FDG_STEM_CONV_BN_RELU) {
       lp.conv[0] = add_conv(ld.c_out, c, 9, ld.stride, h, w);
@@ -196,6 +206,41 @@ bool build_plan(const fdg_module_desc* desc, int save_mode, Plan& p, fdg_status*
         pend.push_back({0, -1, lp.bn[2], 1, (size_t)ld.c_out});
         lp.act[3] = save(Eout);  // p
       }
+    } else if (ld.kind == FDG_STEM_POOL) {
+      // the convolution as a 1x1 contraction over the 448 gathered elements of an output pixel, at half the input resolution
+      const int hc = (h - 1) / 2 + 1, wc = (w - 1) / 2 + 1;
+      lp.conv[0] = add_conv(ld.c_out, 448, 1, 1, hc, wc);
+      p.convs[lp.conv[0]].stem7_ci = c;
+      lp.bn[0] = add_bn(ld.c_out, N * hc * wc);
+      pend.push_back({1, lp.conv[0], -1, 0, 0});
+      pend.push_back({0, -1, lp.bn[0], 0, (size_t)ld.c_out});
+      pend.push_back({0, -1, lp.bn[0], 1, (size_t)ld.c_out});
+      lp.act[0] = save((size_t)N * hc * wc * ld.c_out);  // conv output
+      lp.act[1] = save((size_t)N * hc * wc * ld.c_out);  // relu(bn): what the pool reads
+      p.col_bytes = std::max(p.col_bytes, (size_t)N * hc * wc * 448 * 2);
+    } else if (ld.kind == FDG_INVERTED_RESIDUAL) {
+      const int cm = 6 * c;
+      const size_t Emid_in = (size_t)N * h * w * cm, Emid = (size_t)N * ho * wo * cm;
+      lp.conv[0] = add_conv(cm, c, 1, 1, h, w);
+      lp.bn[0] = add_bn(cm, N * h * w);
+      lp.conv[1] = add_conv(cm, 1, 9, ld.stride, h, w);
+      p.convs[lp.conv[1]].depthwise = true;
+      lp.bn[1] = add_bn(cm, N * ho * wo);
+      lp.conv[3] = add_conv(ld.c_out, cm, 1, 1, ho, wo);
+      lp.bn[3] = add_bn(ld.c_out, N * ho * wo);
+      const int order[3] = {0, 1, 3};
+      for (int q = 0; q < 3; ++q) {
+        const int bn = lp.bn[order[q]];
+        pend.push_back({1, lp.conv[order[q]], -1, 0, 0});
+        pend.push_back({0, -1, bn, 0, (size_t)p.bns[bn].C});
+        pend.push_back({0, -1, bn, 1, (size_t)p.bns[bn].C});
+      }
+      lp.act[0] = save(Emid_in);  // conv1 output
+      lp.act[1] = save(Emid_in);  // relu6(bn1)
+      lp.act[2] = save(Emid);     // depthwise output
+      lp.act[4] = save(Emid);     // relu6(bn2)
+      lp.act[5] = save(Eout);     // conv3 output
+      p.dwscratch_bytes = std::max(p.dwscratch_bytes, dwconv3_wgrad_scratch_bytes(N, h, w, cm, ld.stride));
     } else if (ld.kind == FDG_BOTTLENECK_POSTACT) {
       const int cm = ld.c_out / 4;
       const size_t Emid_in = (size_t)N * h * w * cm, Emid = (size_t)N * ho * wo * cm;
@@ -258,7 +303,7 @@ bool build_plan(const fdg_module_desc* desc, int save_mode, Plan& p, fdg_status*
     t.ext_off = ext;
     if (q.kind == 1) {
       const ConvInfo& ci = p.convs[q.conv];
-      t.count = (size_t)ci.sh.Co * ci.sh.T * ci.sh.Ci;
+      t.count = ci.stem7_ci ? (size_t)ci.sh.Co * ci.stem7_ci * 49 : (size_t)ci.sh.Co * ci.sh.T * ci.sh.Ci;
       t.int_off = ci.p_off;
       t.conv = q.conv;
     } else {
@@ -281,7 +326,7 @@ bool build_plan(const fdg_module_desc* desc, int save_mode, Plan& p, fdg_status*
   if (p.P >= (1ull << 31) || p.warena_elems >= (1ull << 32) || p.maxE >= (1ull << 31)) { *why = FDG_ERR_UNSUPPORTED; return false; }
   for (const ConvInfo& ci : p.convs) p.emit_blocks += emit_blocks_for(ci.sh.Co, ci.sh.Cip, ci.sh.T);
   for (const ConvInfo& ci : p.convs)
-    if (conv_dgrad_feeds_next(ci.sh)) p.stat_rep = (int)(p.stat_floats * kStatWords);
+    if (!ci.depthwise && conv_dgrad_feeds_next(ci.sh)) p.stat_rep = (int)(p.stat_floats * kStatWords);
   const size_t stat_copies = p.stat_rep ? kStatReplicas : 1;
   // workspace layout
   size_t o = 0;
@@ -331,8 +376,12 @@ bool build_plan(const fdg_module_desc* desc, int save_mode, Plan& p, fdg_status*
   // run on two streams at once (delay >= 1, stored form)
   p.o_TPB = take(desc->delay >= 1 && !p.replay ? p.maxE * 4 : 0);
   p.o_dp = take(p.is_top ? (size_t)N * p.head_C * 4 : 0);
-  for (const ConvInfo& ci : p.convs) p.wscratch_bytes = std::max(p.wscratch_bytes, conv_wgrad_scratch_bytes(ci.sh));
+  for (const ConvInfo& ci : p.convs)
+    if (!ci.depthwise) p.wscratch_bytes = std::max(p.wscratch_bytes, conv_wgrad_scratch_bytes(ci.sh));
   p.o_wscratch = take(p.wscratch_bytes);
+  p.o_dwscratch = take(p.dwscratch_bytes);
+  p.o_col = take(p.col_bytes);
+  p.o_colb = (desc->delay >= 1 && !p.replay) ? take(p.col_bytes) : p.o_col;   // as o_TPB: the two may run on two streams
   p.total = o;
   {
     size_t to = 0;
@@ -605,7 +654,8 @@ hipError_t bn_stats(const SlotView& v, const BnInfo& b, const bf16_t* x, hipStre
 // forward apply with the parameters of the slot's snapshot (taken from the current ones just before the forward);
 // moves the running statistics unless this is the replay of a saved forward
 hipError_t bn_apply(const fdg_module* m, const SlotView& v, const BnInfo& b, const bf16_t* x, const float* res,
-                    const BnInfo* b2, const bf16_t* x2, float* out_f32, bf16_t* out_b16, bool replayed, hipStream_t s) {
+                    const BnInfo* b2, const bf16_t* x2, float* out_f32, bf16_t* out_b16, bool replayed, hipStream_t s,
+                    int relu = 1) {
   BnApplyArgs a{};
   a.x = x; a.sums = v.sums(b); a.gamma = v.snap(b.gamma_off); a.beta = v.snap(b.beta_off);
   a.res_f32 = res;
@@ -615,18 +665,21 @@ hipError_t bn_apply(const fdg_module* m, const SlotView& v, const BnInfo& b, con
   }
   a.out_f32 = out_f32; a.out_b16 = out_b16;
   if (!replayed) { a.run_mean = m->running() + b.stat_off; a.run_var = m->running() + b.stat_off + b.C; }
-  a.M = b.M; a.C = b.C; a.eps = m->p.d.bn_eps; a.momentum = m->p.d.bn_momentum; a.relu = 1;
+  a.M = b.M; a.C = b.C; a.eps = m->p.d.bn_eps; a.momentum = m->p.d.bn_momentum; a.relu = relu;
   a.rep_stride = m->p.stat_rep;
   ProfScope ps(m, PC_BN_APPLY, 0, (double)b.M * b.C * (2 + (res ? 4 : 0) + (b2 ? 2 : 0) + (out_f32 ? 4 : 0) + (out_b16 ? 2 : 0)), s);
   return launch_bn_apply(a, s);
 }
 
-// backward through ReLU (mask) and BN with the slot's gamma snapshot
+// backward through ReLU (mask; gate_hi = 6 for ReLU6; mask == nullptr: no activation to gate by) and BN with the slot's gamma
+// snapshot
 hipError_t bn_backward(const fdg_module* m, const SlotView& v, const BnInfo& b, const void* dy, bool dy_f32,
                        const bf16_t* mask, const bf16_t* x, const float* addend, float* out_f32, bf16_t* out_b16,
-                       hipStream_t s) {
+                       hipStream_t s, float gate_hi = 0.f) {
   BnBwdArgs a{};
   a.dy = dy; a.dy_is_f32 = dy_f32 ? 1 : 0; a.mask = mask; a.x = x; a.sums = v.sums(b);
+  a.gate_hi = gate_hi;
+  a.dy_gated = mask ? 0 : 1;
   a.gamma = v.snap(b.gamma_off);
   a.bsums = m->bsums(b);
   a.addend = addend; a.out_f32 = out_f32; a.out_b16 = out_b16;
@@ -775,6 +828,29 @@ fdg_status forward_pass(fdg_module* m, const SlotView& v, const float* x_dev, fl
       } else {
         FDG_TRY(bn_apply(m, v, b3, t_c3, m->S(cur), nullptr, nullptr, m->S(nxt), v.act(L.out_b), replayed, s));
       }
+    } else if (L.kind == FDG_STEM_POOL) {
+      const ConvInfo& c0 = p.convs[L.conv[0]];
+      const BnInfo& b0 = p.bns[L.bn[0]];
+      bf16_t* col = reinterpret_cast<bf16_t*>(m->ws + p.o_col);
+      bf16_t *t_c = v.act(L.act[0]), *t_a = v.act(L.act[1]);
+      FDG_TRY(side_wait_readers(m, col, s));
+      FDG_TRY(launch_im2col7(cur_b, col, N, L.Hi, L.Wi, s));
+      FDG_TRY(mconv_forward(m, c0, col, v.W(c0), nullptr, nullptr, t_c, v.sums(b0), s));
+      FDG_TRY(bn_apply(m, v, b0, t_c, nullptr, nullptr, nullptr, nullptr, t_a, replayed, s));
+      FDG_TRY(launch_maxpool3s2(t_a, m->S(nxt), v.act(L.out_b), N, c0.sh.Hi, c0.sh.Wi, L.c_out, s));
+    } else if (L.kind == FDG_INVERTED_RESIDUAL) {
+      const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]], &c3 = p.convs[L.conv[3]];
+      const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]], &b3 = p.bns[L.bn[3]];
+      bf16_t *t_c1 = v.act(L.act[0]), *t_a1 = v.act(L.act[1]), *t_c2 = v.act(L.act[2]), *t_a2 = v.act(L.act[4]),
+             *t_c3 = v.act(L.act[5]);
+      FDG_TRY(mconv_forward(m, c1, cur_b, v.W(c1), nullptr, nullptr, t_c1, v.sums(b1), s));
+      FDG_TRY(bn_apply(m, v, b1, t_c1, nullptr, nullptr, nullptr, nullptr, t_a1, replayed, s, /*relu6*/ 2));
+      FDG_TRY(launch_dwconv3_fwd(t_a1, v.Wt(c2), t_c2, N, L.Hi, L.Wi, c2.sh.Co, L.stride, s));
+      FDG_TRY(bn_stats(v, b2, t_c2, s));
+      FDG_TRY(bn_apply(m, v, b2, t_c2, nullptr, nullptr, nullptr, nullptr, t_a2, replayed, s, /*relu6*/ 2));
+      FDG_TRY(mconv_forward(m, c3, t_a2, v.W(c3), nullptr, nullptr, t_c3, v.sums(b3), s));
+      const bool adds = L.stride == 1 && L.c_in == L.c_out;
+      FDG_TRY(bn_apply(m, v, b3, t_c3, adds ? m->S(cur) : nullptr, nullptr, nullptr, m->S(nxt), v.act(L.out_b), replayed, s, /*no activation*/ 0));
     } else if (L.kind == FDG_BASIC_PREACT) {
       const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]];
       const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]];
@@ -1065,6 +1141,36 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
           FDG_TRY(mconv_dgrad(m, c1, m->T(0), v.Wt(c1), m->G(cur), t_y, m->G(nxt), m->GB(nxt), s));
         }
       }
+    } else if (L.kind == FDG_STEM_POOL) {
+      // the pool hands every window's gradient to its first maximum; then ReLU, batch norm, and the weight gradient of
+      // the convolution as a 1x1 contraction over the gathered operand rows (gathered again: they are not kept)
+      const ConvInfo& c0 = p.convs[L.conv[0]];
+      const BnInfo& b0 = p.bns[L.bn[0]];
+      bf16_t* col = reinterpret_cast<bf16_t*>(m->ws + p.o_colb);
+      const bf16_t *t_c = v.act(L.act[0]), *t_a = v.act(L.act[1]);
+      FDG_TRY(launch_maxpool3s2_bwd(t_a, m->G(cur), m->TPB(), N, c0.sh.Hi, c0.sh.Wi, L.c_out, s));
+      FDG_TRY(bn_backward(m, v, b0, m->TPB(), true, t_a, t_c, nullptr, nullptr, m->T(0), s));
+      FDG_TRY(side_wait_readers(m, col, s));
+      FDG_TRY(launch_im2col7(in_b, col, N, L.Hi, L.Wi, s));
+      FDG_TRY(mconv_wgrad(m, c0, col, m->T(0), s));
+    } else if (L.kind == FDG_INVERTED_RESIDUAL) {
+      const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]], &c3 = p.convs[L.conv[3]];
+      const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]], &b3 = p.bns[L.bn[3]];
+      const bf16_t *t_c1 = v.act(L.act[0]), *t_a1 = v.act(L.act[1]), *t_c2 = v.act(L.act[2]), *t_a2 = v.act(L.act[4]),
+                   *t_c3 = v.act(L.act[5]);
+      const bool adds = L.stride == 1 && L.c_in == L.c_out;
+      // the block ends in a batch norm: nothing gates the incoming gradient
+      FDG_TRY(bn_backward(m, v, b3, m->G(cur), true, nullptr, t_c3, nullptr, nullptr, m->T(0), s));
+      FDG_TRY(mconv_wgrad(m, c3, t_a2, m->T(0), s));
+      FDG_TRY(mconv_dgrad(m, c3, m->T(0), v.Wt(c3), nullptr, nullptr, nullptr, m->T(1), s));
+      FDG_TRY(bn_backward(m, v, b2, m->T(1), false, t_a2, t_c2, nullptr, nullptr, m->T(0), s, 6.f));
+      FDG_TRY(launch_dwconv3_wgrad(t_a1, m->T(0), m->grads() + c2.p_off, reinterpret_cast<float*>(m->ws + p.o_dwscratch),
+                                   p.dwscratch_bytes, N, L.Hi, L.Wi, c2.sh.Co, L.stride, s));
+      FDG_TRY(side_wait_readers(m, m->T(1), s));
+      FDG_TRY(launch_dwconv3_dgrad(m->T(0), v.Wt(c2), m->T(1), N, L.Hi, L.Wi, c2.sh.Co, L.stride, s));
+      FDG_TRY(bn_backward(m, v, b1, m->T(1), false, t_a1, t_c1, nullptr, nullptr, m->T(0), s, 6.f));
+      FDG_TRY(mconv_wgrad(m, c1, in_b, m->T(0), s));
+      if (need_dx) FDG_TRY(mconv_dgrad(m, c1, m->T(0), v.Wt(c1), adds ? m->G(cur) : nullptr, nullptr, m->G(nxt), m->GB(nxt), s));
     } else {  // pre-activation block: y = conv2(o2) + shortcut
       const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]];
       const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]];
@@ -1137,6 +1243,14 @@ static void ext_to_int(const Plan& p, const float* ext, float* in) {
   for (const ParamTensor& t : p.ptensors) {
     if (t.conv < 0) {
       for (size_t i = 0; i < t.count; ++i) in[t.int_off + i] = ext[t.ext_off + i];
+    } else if (const int s7 = p.convs[t.conv].stem7_ci) {
+      // [Co, ci, 7, 7] -> [Co][kh][kw of 8][c of 8]; the eighth column and the channels beyond ci stay zero
+      const ConvShape& c = p.convs[t.conv].sh;
+      for (int co = 0; co < c.Co; ++co)
+        for (int ci = 0; ci < s7; ++ci)
+          for (int kh = 0; kh < 7; ++kh)
+            for (int kw = 0; kw < 7; ++kw)
+              in[t.int_off + (size_t)co * 448 + kh * 64 + kw * 8 + ci] = ext[t.ext_off + (((size_t)co * s7 + ci) * 7 + kh) * 7 + kw];
     } else {
       const ConvShape& c = p.convs[t.conv].sh;
       for (int co = 0; co < c.Co; ++co)
@@ -1150,6 +1264,13 @@ static void int_to_ext(const Plan& p, const float* in, float* ext) {
   for (const ParamTensor& t : p.ptensors) {
     if (t.conv < 0) {
       for (size_t i = 0; i < t.count; ++i) ext[t.ext_off + i] = in[t.int_off + i];
+    } else if (const int s7 = p.convs[t.conv].stem7_ci) {
+      const ConvShape& c = p.convs[t.conv].sh;
+      for (int co = 0; co < c.Co; ++co)
+        for (int ci = 0; ci < s7; ++ci)
+          for (int kh = 0; kh < 7; ++kh)
+            for (int kw = 0; kw < 7; ++kw)
+              ext[t.ext_off + (((size_t)co * s7 + ci) * 7 + kh) * 7 + kw] = in[t.int_off + (size_t)co * 448 + kh * 64 + kw * 8 + ci];
     } else {
       const ConvShape& c = p.convs[t.conv].sh;
       for (int co = 0; co < c.Co; ++co)
@@ -1301,6 +1422,12 @@ fdg_status fdg_saved_read(const fdg_module* m, int64_t seq, int32_t layer, int32
         if (which == 2 || which == 4) c = cm;
         break;
       case FDG_HEAD_PREACT: has = which == 0; c = L.c_in; h = L.Hi; w = L.Wi; break;
+      case FDG_STEM_POOL: has = which <= 1; h = (L.Hi - 1) / 2 + 1; w = (L.Wi - 1) / 2 + 1; break;
+      case FDG_INVERTED_RESIDUAL:
+        has = which != 3;
+        if (which == 0 || which == 1) { c = 6 * L.c_in; h = L.Hi; w = L.Wi; }
+        if (which == 2 || which == 4) c = 6 * L.c_in;
+        break;
       default: break;
     }
     if (!has) return FDG_ERR_INVALID_ARG;

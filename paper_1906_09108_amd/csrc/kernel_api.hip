@@ -233,4 +233,40 @@ int fdgk_nhwc_to_nchw(const float* src, float* dst, int n, int c, int hw, int cp
   return (int)launch_nhwc_to_nchw(src, dst, n, c, hw, cp, st(hip_stream));
 }
 
+int fdgk_im2col7(const void* x8_b16, void* col_b16, int n, int h, int w, void* hip_stream) {
+  if (!x8_b16 || !col_b16) return (int)hipErrorInvalidValue;
+  return (int)launch_im2col7(static_cast<const bf16_t*>(x8_b16), static_cast<bf16_t*>(col_b16), n, h, w, st(hip_stream));
+}
+
+int fdgk_maxpool3s2(const void* x_b16, float* y_f32, void* y_b16, int n, int h, int w, int c, void* hip_stream) {
+  if (!x_b16) return (int)hipErrorInvalidValue;
+  return (int)launch_maxpool3s2(static_cast<const bf16_t*>(x_b16), y_f32, static_cast<bf16_t*>(y_b16), n, h, w, c, st(hip_stream));
+}
+
+int fdgk_maxpool3s2_bwd(const void* x_b16, const float* dy_f32, float* dx_f32, int n, int h, int w, int c, void* hip_stream) {
+  if (!x_b16 || !dy_f32 || !dx_f32) return (int)hipErrorInvalidValue;
+  return (int)launch_maxpool3s2_bwd(static_cast<const bf16_t*>(x_b16), dy_f32, dx_f32, n, h, w, c, st(hip_stream));
+}
+
+int fdgk_dwconv3_fwd(const void* x_b16, const void* wt_b16, void* y_b16, int n, int h, int w, int c, int stride, void* hip_stream) {
+  if (!x_b16 || !wt_b16 || !y_b16) return (int)hipErrorInvalidValue;
+  return (int)launch_dwconv3_fwd(static_cast<const bf16_t*>(x_b16), static_cast<const bf16_t*>(wt_b16), static_cast<bf16_t*>(y_b16), n, h,
+                                 w, c, stride, st(hip_stream));
+}
+
+int fdgk_dwconv3_dgrad(const void* dy_b16, const void* wt_b16, void* dx_b16, int n, int h, int w, int c, int stride, void* hip_stream) {
+  if (!dy_b16 || !wt_b16 || !dx_b16) return (int)hipErrorInvalidValue;
+  return (int)launch_dwconv3_dgrad(static_cast<const bf16_t*>(dy_b16), static_cast<const bf16_t*>(wt_b16), static_cast<bf16_t*>(dx_b16), n,
+                                   h, w, c, stride, st(hip_stream));
+}
+
+size_t fdgk_dwconv3_wgrad_scratch_bytes(int n, int h, int w, int c, int stride) { return dwconv3_wgrad_scratch_bytes(n, h, w, c, stride); }
+
+int fdgk_dwconv3_wgrad(const void* x_b16, const void* dy_b16, float* dw_f32, float* scratch_f32, size_t scratch_bytes, int n, int h,
+                       int w, int c, int stride, void* hip_stream) {
+  if (!x_b16 || !dy_b16 || !dw_f32) return (int)hipErrorInvalidValue;
+  return (int)launch_dwconv3_wgrad(static_cast<const bf16_t*>(x_b16), static_cast<const bf16_t*>(dy_b16), dw_f32, scratch_f32,
+                                   scratch_bytes, n, h, w, c, stride, st(hip_stream));
+}
+
 }  // extern "C"

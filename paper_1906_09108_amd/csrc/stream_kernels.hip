@@ -327,6 +327,10 @@ __global__ __launch_bounds__(kThreads) void bn_apply_kernel(BnApplyArgs a, int C
     if (a.relu) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) f[i] = fmaxf(f[i], 0.f);
+      if (a.relu == 2) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[i] = fminf(f[i], 6.f);
+      }
     }
     if (a.out_f32) store8_f32(a.out_f32 + o, f);
     if (a.out_b16) *reinterpret_cast<uint4*>(a.out_b16 + o) = pack8(f);
@@ -364,7 +368,7 @@ hipError_t launch_bn_apply(const BnApplyArgs& a, hipStream_t s) {
 
 // ---- BN backward ---------------------------------------------------------------------------------
 template <bool DY_F32>
-__device__ __forceinline__ void load_masked_dy(const void* dy, const bf16_t* mask, size_t o, float (&g)[8]) {
+__device__ __forceinline__ void load_masked_dy(const void* dy, const bf16_t* mask, float hi, size_t o, float (&g)[8]) {
   if (DY_F32)
     load8_f32(reinterpret_cast<const float*>(dy) + o, g);
   else
@@ -374,8 +378,10 @@ __device__ __forceinline__ void load_masked_dy(const void* dy, const bf16_t* mas
   unpack8(*reinterpret_cast<const uint4*>(mask + o), mk);
 #pragma unroll
   for (int i = 0; i < 8; ++i)
-    if (!(mk[i] > 0.f)) g[i] = 0.f;
+    if (!(mk[i] > 0.f) || mk[i] >= hi) g[i] = 0.f;
 }
+// the upper end of the gate: +inf unless the activation was clamped (ReLU6)
+__device__ __forceinline__ float gate_top(float gate_hi) { return gate_hi > 0.f ? gate_hi : __builtin_inff(); }
 
 // batch mean and 1 / sqrt(variance + eps) of the 8 channels from c0 on, see LaneShare
 template <int COPIES>
@@ -424,7 +430,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_reduce_kernel(BnBwdArgs a, in
     for (int row = row_lo + rl; row < row_hi; row += RL) {
       const size_t o = (size_t)row * C + cg * 8;
       float g[8], xv[8];
-      load_masked_dy<DY_F32>(a.dy, a.mask, o, g);
+      load_masked_dy<DY_F32>(a.dy, a.mask, gate_top(a.gate_hi), o, g);
       unpack8(*reinterpret_cast<const uint4*>(a.x + o), xv);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
@@ -437,7 +443,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_reduce_kernel(BnBwdArgs a, in
 }
 
 hipError_t launch_bn_bwd_reduce(const BnBwdArgs& a, hipStream_t s) {
-  if (a.C % 8 != 0 || a.C > 2048 || a.M <= 0 || !a.mask) return hipErrorInvalidValue;
+  if (a.C % 8 != 0 || a.C > 2048 || a.M <= 0 || (!a.mask && !a.dy_gated)) return hipErrorInvalidValue;
   const ReduceShape r = reduce_shape(a.M, a.C);
   const size_t sm = 2 * (size_t)kThreads * 8 * sizeof(float);
 #define FDG_LAUNCH_REDUCE(F32, CP) \
@@ -576,7 +582,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(BnBwdArgs a, int
       unpack8(pmk[j], mk);
 #pragma unroll
       for (int i = 0; i < 8; ++i)
-        if (!(mk[i] > 0.f)) g[i] = 0.f;
+        if (!(mk[i] > 0.f) || mk[i] >= gate_top(a.gate_hi)) g[i] = 0.f;
     }
     finish_row(row, g, px[j]);
   }
@@ -584,7 +590,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(BnBwdArgs a, int
   for (int row = row_lo + rl + NPRE * RL; row < row_hi; row += RL) {
     const size_t o = (size_t)row * C + c0;
     float g[8];
-    load_masked_dy<DY_F32>(a.dy, a.mask, o, g);
+    load_masked_dy<DY_F32>(a.dy, a.mask, gate_top(a.gate_hi), o, g);
     finish_row(row, g, *reinterpret_cast<const uint4*>(a.x + o));
   }
 }

@@ -8,7 +8,9 @@ from .binding import _ptr, _stream_handle, load
 
 KERNEL_EXPORTS = ["fdgk_conv_fwd", "fdgk_conv_dgrad", "fdgk_conv_dgrad_gated", "fdgk_conv_dgrad_feeding_next", "fdgk_conv_dgrad_gates", "fdgk_bn_bwd_gated", "fdgk_conv_wgrad", "fdgk_conv_wgrad_scratch_bytes", "fdgk_bn_stats", "fdgk_bn_apply",
                   "fdgk_bn_bwd", "fdgk_sgd", "fdgk_bn_bwd_static", "fdgk_bn_bwd_static_max_c", "fdgk_sums_bytes", "fdgk_sums_read",
-                  "fdgk_avgpool", "fdgk_fc_fwd", "fdgk_softmax_ce", "fdgk_fc_bwd", "fdgk_pool_bwd", "fdgk_nchw_to_nhwc", "fdgk_nhwc_to_nchw"]
+                  "fdgk_avgpool", "fdgk_fc_fwd", "fdgk_softmax_ce", "fdgk_fc_bwd", "fdgk_pool_bwd", "fdgk_nchw_to_nhwc", "fdgk_nhwc_to_nchw",
+                  "fdgk_im2col7", "fdgk_maxpool3s2", "fdgk_maxpool3s2_bwd", "fdgk_dwconv3_fwd", "fdgk_dwconv3_dgrad",
+                  "fdgk_dwconv3_wgrad_scratch_bytes", "fdgk_dwconv3_wgrad"]
 _ready = False
 
 
@@ -40,12 +42,20 @@ def _lib():
         lib.fdgk_pool_bwd.argtypes = [vp, vp, vp, i, i, i, vp]
         lib.fdgk_nchw_to_nhwc.argtypes = [vp, vp, vp, i, i, i, i, f, vp]
         lib.fdgk_nhwc_to_nchw.argtypes = [vp, vp, i, i, i, i, vp]
+        lib.fdgk_im2col7.argtypes = [vp, vp, i, i, i, vp]
+        lib.fdgk_maxpool3s2.argtypes = [vp, vp, vp, i, i, i, i, vp]
+        lib.fdgk_maxpool3s2_bwd.argtypes = [vp, vp, vp, i, i, i, i, vp]
+        lib.fdgk_dwconv3_fwd.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
+        lib.fdgk_dwconv3_dgrad.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
+        lib.fdgk_dwconv3_wgrad_scratch_bytes.argtypes = [i, i, i, i, i]
+        lib.fdgk_dwconv3_wgrad.argtypes = [vp, vp, vp, vp, sz, i, i, i, i, i, vp]
         for n in KERNEL_EXPORTS:
             if getattr(lib, n).argtypes is None:   # a pointer passed without a declared type would be cut to 32 bits
                 raise RuntimeError(f"{n}: argument types not declared")
             getattr(lib, n).restype = i
         lib.fdgk_conv_wgrad_scratch_bytes.restype = sz
         lib.fdgk_sums_bytes.restype = sz
+        lib.fdgk_dwconv3_wgrad_scratch_bytes.restype = sz
         _ready = True
     return lib
 
@@ -188,3 +198,34 @@ def fdgk_nchw_to_nhwc(src, dst_f32, dst_b16, n, c, hw, cp, scale=1.0, stream=Non
 
 def fdgk_nhwc_to_nchw(src, dst, n, c, hw, cp, stream=None):
     _ok(_lib().fdgk_nhwc_to_nchw(_ptr(src), _ptr(dst), n, c, hw, cp, _stream_handle(stream)), "fdgk_nhwc_to_nchw")
+
+
+def fdgk_im2col7(x8_b16, col_b16, n, h, w, stream=None):
+    _ok(_lib().fdgk_im2col7(_ptr(x8_b16), _ptr(col_b16), n, h, w, _stream_handle(stream)), "fdgk_im2col7")
+
+
+def fdgk_maxpool3s2(x_b16, y_f32, y_b16, n, h, w, c, stream=None):
+    _ok(_lib().fdgk_maxpool3s2(_ptr(x_b16), _ptr(y_f32), _ptr(y_b16), n, h, w, c, _stream_handle(stream)), "fdgk_maxpool3s2")
+
+
+def fdgk_maxpool3s2_bwd(x_b16, dy_f32, dx_f32, n, h, w, c, stream=None):
+    _ok(_lib().fdgk_maxpool3s2_bwd(_ptr(x_b16), _ptr(dy_f32), _ptr(dx_f32), n, h, w, c, _stream_handle(stream)), "fdgk_maxpool3s2_bwd")
+
+
+def fdgk_dwconv3_fwd(x_b16, wt_b16, y_b16, n, h, w, c, stride, stream=None):
+    _ok(_lib().fdgk_dwconv3_fwd(_ptr(x_b16), _ptr(wt_b16), _ptr(y_b16), n, h, w, c, stride, _stream_handle(stream)), "fdgk_dwconv3_fwd")
+
+
+def fdgk_dwconv3_dgrad(dy_b16, wt_b16, dx_b16, n, h, w, c, stride, stream=None):
+    _ok(_lib().fdgk_dwconv3_dgrad(_ptr(dy_b16), _ptr(wt_b16), _ptr(dx_b16), n, h, w, c, stride, _stream_handle(stream)),
+        "fdgk_dwconv3_dgrad")
+
+
+def fdgk_dwconv3_wgrad_scratch_bytes(n, h, w, c, stride) -> int:
+    return int(_lib().fdgk_dwconv3_wgrad_scratch_bytes(n, h, w, c, stride))
+
+
+def fdgk_dwconv3_wgrad(x_b16, dy_b16, dw_f32, scratch_f32, n, h, w, c, stride, stream=None):
+    nbytes = 0 if scratch_f32 is None else scratch_f32.numel() * scratch_f32.element_size()
+    _ok(_lib().fdgk_dwconv3_wgrad(_ptr(x_b16), _ptr(dy_b16), _ptr(dw_f32), _ptr(scratch_f32), nbytes, n, h, w, c, stride,
+                                  _stream_handle(stream)), "fdgk_dwconv3_wgrad")

@@ -26,8 +26,8 @@ import numpy as np
 
 import fdg_workloads as W
 from fdg_workloads import ModuleSpec
-from oracle.fdg_oracle import (BASIC_POSTACT, BASIC_PREACT, BOTTLENECK_POSTACT, HEAD_POSTACT, HEAD_PREACT, STEM, OracleModule,
-                               _Flat, oracle_param_layout)
+from oracle.fdg_oracle import (BASIC_POSTACT, BASIC_PREACT, BOTTLENECK_POSTACT, HEAD_POSTACT, HEAD_PREACT, INVERTED_RESIDUAL, STEM,
+                               STEM_POOL, OracleModule, _Flat, oracle_param_layout)
 
 # which saved tensor (fdg_saved_read) is which oracle quantity, per layer kind: (which, tape key | "bn:<tag>")
 SAVED = {
@@ -37,6 +37,8 @@ SAVED = {
     BOTTLENECK_POSTACT: [(0, "bn:bn1"), (1, "a1"), (2, "bn:bn2"), (3, "bn:bnp"), (4, "a2"), (5, "bn:bn3")],
     HEAD_POSTACT: [],
     HEAD_PREACT: [(0, "o")],
+    STEM_POOL: [(0, "bn:bn"), (1, "a")],
+    INVERTED_RESIDUAL: [(0, "bn:bn1"), (1, "a1"), (2, "bn:bn2"), (4, "a2"), (5, "bn:bn3")],
 }
 # batch norms of a layer kind: tag -> which saved tensor is its input (7 = the layer input)
 BN_INPUT = {
@@ -46,6 +48,8 @@ BN_INPUT = {
     BOTTLENECK_POSTACT: {"bn1": 0, "bn2": 2, "bn3": 5, "bnp": 3},
     HEAD_POSTACT: {},
     HEAD_PREACT: {"bn": 7},
+    STEM_POOL: {"bn": 0},
+    INVERTED_RESIDUAL: {"bn1": 0, "bn2": 2, "bn3": 5},
 }
 
 
@@ -140,10 +144,12 @@ def _tape_from_gpu(gpu, om: OracleModule, th: _Flat, L, seq: int, i: int) -> Dic
         xin = cache[which]
         _, mean, _, invstd = om.k.bn_fwd(xin, th[f"0.{tag}.gamma"], th[f"0.{tag}.beta"], om.spec.bn_eps)
         t[f"0.{tag}"] = (xin, mean, invstd)
-    if L.kind in (BASIC_POSTACT, BOTTLENECK_POSTACT):
+    if L.kind in (BASIC_POSTACT, BOTTLENECK_POSTACT, INVERTED_RESIDUAL):
         t["a1"] = sv(1)
-    if L.kind == BOTTLENECK_POSTACT:
+    if L.kind in (BOTTLENECK_POSTACT, INVERTED_RESIDUAL):
         t["a2"] = sv(4)
+    if L.kind == STEM_POOL:
+        t["a"] = sv(1)
     if L.kind == BASIC_PREACT:
         t["o1"], t["o2"] = sv(0), sv(2)
     if L.kind in (STEM, BASIC_POSTACT, BOTTLENECK_POSTACT):

@@ -564,3 +564,104 @@ def test_layout_kernels(case):
     assert np.array_equal(d16.to(t.float32).cpu().numpy()[..., :c], bf16_round(x.transpose(0, 2, 3, 1)))
     assert K.fdgk_nchw_to_nhwc(src, None, None, n, c, h * w, cp, 1.0, check=False) != 0
     assert K.fdgk_nchw_to_nhwc(src, None, d16, n, c, h * w, c - 1, 1.0, check=False) != 0
+
+
+# ---- layers of the Tiny-ImageNet networks: 7x7 stem as gathered rows, max-pool, depthwise convolution ----------------
+@pytest.mark.parametrize("case", [(4, 64, 64, 3, 64), (3, 13, 14, 3, 16), (2, 9, 7, 5, 8)])
+def test_stem7_as_gathered_rows_and_a_1x1_contraction(case):
+    """conv7x7 / stride 2 / padding 3 = fdgk_im2col7 followed by fdgk_conv_fwd with ksize 1 over 448 elements, and its weight
+    gradient fdgk_conv_wgrad on the same rows; compared with the oracle's 7x7 convolution."""
+    from paper_1906_09108_amd import kernels as K
+    t = _torch()
+    n, h, w, ci, co = case
+    print("stem7 case", case, flush=True)
+    rng = np.random.default_rng(70 + h)
+    x = bf16_round(rng.standard_normal((n, ci, h, w)).astype(np.float32))
+    wgt = bf16_round((rng.standard_normal((co, ci, 7, 7)) * np.sqrt(2.0 / (49 * ci))).astype(np.float32))
+    ho, wo = (h - 1) // 2 + 1, (w - 1) // 2 + 1
+    x8 = to_dev_nhwc_b16(x, 8)
+    col = t.full((n, ho, wo, 448), 3.0, dtype=t.bfloat16, device="cuda:0")
+    K.fdgk_im2col7(x8, col, n, h, w)
+    # the rows themselves: exact copies
+    colh = col.to(t.float32).cpu().numpy().reshape(n, ho, wo, 7, 8, 8)
+    xp = np.zeros((n, h + 6, w + 8, 8), np.float32)
+    xp[:, 3:3 + h, 3:3 + w, :ci] = x.transpose(0, 2, 3, 1)
+    for kh in range(7):
+        for kw in range(8):
+            want = xp[:, kh:kh + 2 * ho:2, kw:kw + 2 * wo:2, :] if kw < 7 else 0.0
+            assert np.array_equal(colh[:, :, :, kh, kw, :], np.broadcast_to(want, (n, ho, wo, 8))), (kh, kw)
+    # weights in the same order: [co][kh][kw of 8][c of 8]
+    w448 = np.zeros((co, 7, 8, 8), np.float32)
+    w448[:, :, :7, :ci] = wgt.transpose(0, 2, 3, 1)
+    w_dev = t.from_numpy(w448.reshape(co, 448)).to(t.bfloat16).cuda()
+    y = t.empty((n, ho, wo, co), dtype=t.float32, device="cuda:0")
+    K.fdgk_conv_fwd(col, w_dev, None, y, None, None, n, ho, wo, 448, co, 1, 1)
+    ref = K32.conv_fwd(x, wgt, 2, 3)
+    assert rel(nhwc_to_nchw(y), ref) <= F32_TOL
+    dy = bf16_round(rng.standard_normal(ref.shape).astype(np.float32))
+    dw = t.empty((co, 448), dtype=t.float32, device="cuda:0")
+    nb = K.fdgk_conv_wgrad_scratch_bytes(n, ho, wo, 448, co, 1, 1)
+    scratch = t.empty(max(nb // 4, 1), dtype=t.float32, device="cuda:0")
+    K.fdgk_conv_wgrad(col, to_dev_nhwc_b16(dy), dw, scratch, n, ho, wo, 448, co, 1, 1, overwrite=True)
+    dwh = dw.cpu().numpy().reshape(co, 7, 8, 8)
+    ref_dw = K32.conv_bwd_weight(x, dy, 7, 2, 3)
+    assert rel(dwh[:, :, :7, :ci].transpose(0, 3, 1, 2), ref_dw) <= F32_TOL
+    assert not dwh[:, :, 7, :].any() and not dwh[:, :, :, ci:].any()       # the padding of the layout gets no gradient
+
+
+@pytest.mark.parametrize("case", [(8, 32, 32, 64), (3, 7, 9, 16), (2, 8, 8, 24), (1, 1, 1, 8), (2, 33, 32, 64)])
+def test_maxpool_forward_and_backward(case):
+    from paper_1906_09108_amd import kernels as K
+    t = _torch()
+    n, h, w, c = case
+    print("maxpool case", case, flush=True)
+    rng = np.random.default_rng(80 + h + c)
+    # a ReLU output in bf16: many zeros and many equal values, so ties are common and the tie rule matters
+    x = bf16_round(np.maximum(rng.standard_normal((n, c, h, w)), 0).astype(np.float32))
+    x = bf16_round(np.round(x * 4) / 4)
+    ho, wo = (h - 1) // 2 + 1, (w - 1) // 2 + 1
+    xd = to_dev_nhwc_b16(x)
+    y32 = t.empty((n, ho, wo, c), dtype=t.float32, device="cuda:0")
+    y16 = t.empty((n, ho, wo, c), dtype=t.bfloat16, device="cuda:0")
+    K.fdgk_maxpool3s2(xd, y32, y16, n, h, w, c)
+    ref = K32.maxpool_fwd(x, 3, 2, 1)
+    assert np.array_equal(nhwc_to_nchw(y32), ref)
+    assert np.array_equal(nhwc_to_nchw(y16), ref)
+    dy = rng.standard_normal(ref.shape).astype(np.float32)
+    dx = t.full((n, h, w, c), 9.0, dtype=t.float32, device="cuda:0")
+    K.fdgk_maxpool3s2_bwd(xd, to_dev_nhwc_f32(dy), dx, n, h, w, c)
+    ref_dx = K32.maxpool_bwd(x, dy, 3, 2, 1)
+    assert rel(nhwc_to_nchw(dx), ref_dx) <= 1e-6          # sums of at most four terms
+
+
+@pytest.mark.parametrize("case", [(8, 16, 16, 192, 1), (8, 32, 32, 192, 2), (3, 7, 9, 24, 1), (2, 9, 7, 40, 2), (16, 8, 8, 576, 1), (1, 1, 1, 8, 1)])
+def test_depthwise_convolution_kernels(case):
+    from paper_1906_09108_amd import kernels as K
+    t = _torch()
+    n, h, w, c, s = case
+    print("depthwise case", case, flush=True)
+    rng = np.random.default_rng(90 + h + c + s)
+    x = bf16_round(rng.standard_normal((n, c, h, w)).astype(np.float32))
+    wgt = bf16_round((rng.standard_normal((c, 1, 3, 3)) * np.sqrt(2.0 / 9)).astype(np.float32))
+    wt = t.from_numpy(np.ascontiguousarray(wgt.reshape(c, 9).T)).to(t.bfloat16).cuda()     # [9][c]
+    ho, wo = (h - 1) // s + 1, (w - 1) // s + 1
+    xd = to_dev_nhwc_b16(x)
+    y = t.empty((n, ho, wo, c), dtype=t.bfloat16, device="cuda:0")
+    K.fdgk_dwconv3_fwd(xd, wt, y, n, h, w, c, s)
+    ref = K32.dwconv_fwd(x, wgt, s, 1)
+    assert rel(nhwc_to_nchw(y), ref) <= B16_TOL
+    dy = bf16_round(rng.standard_normal(ref.shape).astype(np.float32))
+    dyd = to_dev_nhwc_b16(dy)
+    dx = t.empty((n, h, w, c), dtype=t.bfloat16, device="cuda:0")
+    K.fdgk_dwconv3_dgrad(dyd, wt, dx, n, h, w, c, s)
+    assert rel(nhwc_to_nchw(dx), K32.dwconv_bwd_data(dy, wgt, x.shape, s, 1)) <= B16_TOL
+    nb = K.fdgk_dwconv3_wgrad_scratch_bytes(n, h, w, c, s)
+    assert nb > 0
+    dws = []
+    for _ in range(2):
+        scratch = t.full((nb // 4,), 5.0, dtype=t.float32, device="cuda:0")
+        dw = t.full((c, 9), 5.0, dtype=t.float32, device="cuda:0")
+        K.fdgk_dwconv3_wgrad(xd, dyd, dw, scratch, n, h, w, c, s)
+        dws.append(dw.cpu().numpy())
+    assert rel(dws[0].reshape(c, 1, 3, 3), K32.dwconv_bwd_weight(x, dy, 3, s, 1)) <= F32_TOL
+    assert np.array_equal(dws[0], dws[1])                  # fixed-order sums: the same bits every time

@@ -149,7 +149,7 @@ def test_config1_every_layer():
     _judge_plain(plain, "cfg1")
 
 
-@pytest.mark.parametrize("idx,n", [(2, 16), (3, 16), (5, 8), (6, 8), (7, 4), (8, 8), (8, 25)])
+@pytest.mark.parametrize("idx,n", [(2, 16), (3, 16), (5, 8), (6, 8), (7, 4), (8, 8), (8, 25), (9, 4), (10, 8)])
 def test_configs_reduced_batch_every_layer(idx, n):
     """The other benchmark modules at their real layer shapes and delays, with a batch the oracle finishes in seconds:
     the forward of the newest batch and the delayed backward of the oldest one, after an update has moved the weights
@@ -159,6 +159,10 @@ def test_configs_reduced_batch_every_layer(idx, n):
         # 150 blocks amplify the synthetic noise gradient to 3e3 (the oracle's too): one update at lr = 0.1 would move
         # the weights by hundreds and the next forward would overflow.  A small step keeps the module a network.
         spec.lr = 1e-5
+    if idx == 10:
+        # the same for the depthwise filters: nine weights per channel collect the noise gradient of all pixels (up to 70
+        # against weights of order one), and one update at lr = 0.1 would leave a network whose activations saturate
+        spec.lr = 1e-3
     print(f"case cfg{idx} n={n} layer by layer", flush=True)
     plain = []
     _judge(_run(spec, seed=0, steps_after_warmup=2, plain=plain), f"cfg{idx} n={n}")

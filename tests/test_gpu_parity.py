@@ -25,6 +25,9 @@ STRICT = {
     "preact_widen": ModuleSpec(16, 24, 17, 15, [Layer(W.BASIC_PREACT, 24, 40, 1)], delay=0, beta=0.7, **H),
     "head_postact": ModuleSpec(64, 32, 8, 8, [Layer(W.BASIC_POSTACT, 32, 32, 1), Layer(W.HEAD_POSTACT, 32)], delay=0,
                                num_classes=7, **H),
+    # the ImageNet stem: 7x7 convolution of stride 2, batch norm, ReLU, 3x3 max-pool of stride 2 (bottom modules only)
+    "stem_pool": ModuleSpec(16, 3, 64, 64, [Layer(W.STEM_POOL, 3, 16, 4)], delay=0, is_bottom=True, beta=0.5, **H),
+    "stem_pool_delay1_odd": ModuleSpec(8, 3, 61, 67, [Layer(W.STEM_POOL, 3, 32, 4)], delay=1, is_bottom=True, beta=0.5, **H),
 }
 
 # Ragged, tiny or wide modules: partial tiles everywhere; a single ReLU tie is worth several per cent of
@@ -52,6 +55,13 @@ ENVELOPE = {
                                     delay=0, beta=0.5, **H),
     "bottleneck_wide_head": ModuleSpec(16, 256, 14, 14, [Layer(W.BOTTLENECK_POSTACT, 256, 512, 1), Layer(W.BOTTLENECK_POSTACT, 512, 512, 2),
                                                          Layer(W.HEAD_POSTACT, 512)], delay=0, num_classes=10, **H),
+    # MobileNet-v2's inverted residual block: two ReLU6 gates and a depthwise convolution between two 1x1 convolutions
+    "inverted_residual_identity": ModuleSpec(16, 16, 16, 16, [Layer(W.INVERTED_RESIDUAL, 16, 16, 1)], delay=0, beta=0.5, **H),
+    "inverted_residual_stride2_delay1": ModuleSpec(16, 16, 32, 32, [Layer(W.INVERTED_RESIDUAL, 16, 24, 2)], delay=1, beta=0.5, **H),
+    "inverted_residual_ragged_stack": ModuleSpec(3, 8, 9, 7, [Layer(W.INVERTED_RESIDUAL, 8, 16, 1), Layer(W.INVERTED_RESIDUAL, 16, 16, 1),
+                                                             Layer(W.INVERTED_RESIDUAL, 16, 24, 2)], delay=0, beta=0.5, **H),
+    "stem_pool_stack": ModuleSpec(16, 3, 64, 64, [Layer(W.STEM_POOL, 3, 16, 4), Layer(W.BASIC_POSTACT, 16, 16, 1),
+                                                  Layer(W.INVERTED_RESIDUAL, 16, 16, 1)], delay=1, is_bottom=True, beta=0.5, **H),
     "bottom_stack_delay2": ModuleSpec(4, 3, 16, 16, [Layer(W.STEM, 3, 16, 1), Layer(W.BASIC_POSTACT, 16, 16, 1),
                                                      Layer(W.BASIC_POSTACT, 16, 32, 2), Layer(W.BASIC_POSTACT, 32, 32, 1)],
                                       delay=2, is_bottom=True, beta=0.2, **H),

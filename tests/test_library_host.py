@@ -16,7 +16,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared(header, prefix):
     text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(" + prefix + r"[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(" + prefix + r"[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -37,7 +37,7 @@ def test_status_strings():
     assert b"queue" in lib.fdg_status_string(4)
 
 
-@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
 def test_workspace_bytes_of_benchmark_configs(idx):
     spec = W.config(idx)
     b = binding.fdg_module_workspace_bytes(spec)
@@ -88,7 +88,10 @@ def test_invalid_descriptors_are_rejected():
                 ModuleSpec(2, 16, 8, 8, [Layer(W.BASIC_POSTACT, 16, 12, 1)]),         # channels not a multiple of 8
                 ModuleSpec(0, 16, 8, 8, [Layer(W.BASIC_POSTACT, 16, 16, 1)]),
                 ModuleSpec(2, 16, 8, 8, [Layer(W.BOTTLENECK_POSTACT, 16, 48, 1)]),    # a quarter of 48 is not a multiple of 8
-                ModuleSpec(2, 16, 8, 8, [Layer(6, 16, 16, 1)])):                      # no such layer kind
+                ModuleSpec(2, 16, 8, 8, [Layer(8, 16, 16, 1)]),                       # no such layer kind
+                ModuleSpec(2, 3, 8, 8, [Layer(W.STEM_POOL, 3, 16, 2)], is_bottom=True),  # the stem halves twice: stride 4
+                ModuleSpec(2, 3, 8, 8, [Layer(W.STEM_POOL, 3, 16, 4)], is_bottom=False),  # it has no input gradient
+                ModuleSpec(2, 16, 8, 8, [Layer(W.INVERTED_RESIDUAL, 16, 16, 4)])):
         assert binding.fdg_module_workspace_bytes(bad) == 0
     bottleneck = ModuleSpec(2, 16, 8, 8, [Layer(W.BOTTLENECK_POSTACT, 16, 64, 2), Layer(W.BOTTLENECK_POSTACT, 64, 64, 1)])
     plain = ModuleSpec(2, 16, 8, 8, [Layer(W.BOTTLENECK_POSTACT, 16, 64, 2)])
