@@ -41,6 +41,15 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 0xf) | ((N >> 4) << 14) | (0x7 << 4) | (0xf << 8));
 }
 
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 // Four waves: wave_m = wave & 1 owns 64 of the tile's 128 pixels and ALL of its BN channels as 2 x (BN/32)
 // accumulator blocks of 32x32; wk = wave >> 1 takes one 32-channel half of every 64-channel k-chunk.  So a
 // wave reads 2 + BN/32 operand fragments for every 2 * BN/32 MFMAs (the best ratio four waves can get on a
@@ -186,16 +195,275 @@ __device__ __forceinline__ void gather_dma_body(const GatherConvArgs& a, int m_t
   combine_and_store32<FN, BN, F32S>(b, acc, m0, c0, wave_m, wk, lane, smem);
 }
 
-template <int BN, int STAGES, bool KTAIL>
-__global__ __launch_bounds__(256) void conv_gather_dma_kernel(GatherConvArgs a, int m_tiles, int n_tiles) {
-  gather_dma_body<BN, STAGES, KTAIL>(a, m_tiles, n_tiles);
-}
-// The same within 256 registers, so that two workgroups (two waves per SIMD) fit a compute unit: for the two-stage form.
+// Within 256 registers, so that two workgroups (two waves per SIMD) fit a compute unit: the two-stage form.
 // F32S: sums of the fp32 values in the output stage (GatherConvArgs::stats_f32), for a data gradient that feeds the layer below.
 template <int BN, int STAGES, bool KTAIL, bool F32S>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void conv_gather_dma_pair_kernel(
     GatherConvArgs a, int m_tiles, int n_tiles) {
   gather_dma_body<BN, STAGES, KTAIL, F32S>(a, m_tiles, n_tiles);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Gather form with the hand-pinned pipeline of the patch kernel below (its description of the half steps, the
+// fragment sets and the explicit waits applies word for word): what the patch form cannot take -- stride 2, 1x1,
+// the parity classes of a stride-2 data gradient, images wider than 32 pixels.
+// ------------------------------------------------------------------------------------------------
+// A step is one 64-channel block of one tap (taps outer, channel blocks inner).  Its stage holds 128 pixel rows and
+// BN weight rows; WS stages, the group of loads for step i + WS - 1 goes out during step i, one load every SPACING
+// slots after the barrier of that step.  A pixel row that the tap moves outside the image (or that does not exist)
+// is loaded from a 16-byte zero word: whether it does is one bit per tap and load, worked out once per lane.
+// The per-tap offsets sit in the lanes of two registers (lane t: tap t) and are fetched with a lane read, so the
+// loop reads no kernel argument by a run-time index.  Steps may number anything from 0 (a class of a 1x1 stride-2
+// data gradient that no tap reaches: its result is the addend, or zero) upwards.
+template <int BN, int WS, bool KTAIL>
+__global__ __launch_bounds__(256) void conv_gather_pipe_kernel(GatherConvArgs a, int m_tiles, int n_tiles) {
+  constexpr int BM = 128, ROWB = 128;
+  static_assert(BN % 32 == 0, "whole 32x32 blocks");
+  constexpr int JX = BM / 32, JW = BN / 32, NJ = JX + JW;
+  constexpr int FM = 2, FN = BN / 32;
+  constexpr int SBYTES = (BM + BN) * ROWB;
+  static_assert(WS >= 3 && (WS - 2) * NJ < 64, "vmcnt range");
+  static_assert((size_t)WS * SBYTES >= (size_t)4 * FN * 16 * 256 && (size_t)WS * SBYTES >= (size_t)4 * out_stage_bytes(BN) + stats_stage_bytes(BN), "room for the output stage");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // WS * SBYTES
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave_m = wave & 1, wk = wave >> 1;
+
+  GatherConvArgs b = a;      // the geometry this workgroup works on
+  int t = blockIdx.x, cls = 0;
+  if (a.nclass > 1) {
+    // classes are ordered by decreasing work, so the plain order lets the dispatcher balance them
+    while (cls + 1 < a.nclass && t >= a.cls_start[cls + 1]) ++cls;
+    t -= a.cls_start[cls];
+    b.OH = a.cOH[cls]; b.OW = a.cOW[cls]; b.ooh = a.cooh[cls]; b.oow = a.coow[cls]; b.ntaps = a.cntaps[cls];
+  } else {
+    const int total = m_tiles * n_tiles;
+    if ((total & 7) == 0) t = (blockIdx.x & 7) * (total >> 3) + (blockIdx.x >> 3);
+  }
+  const int Mtot = b.N * b.OH * b.OW;
+  const int m0 = (t / n_tiles) * BM, c0 = (t % n_tiles) * BN;
+  const int ntaps = b.ntaps;
+  const int cpc = (a.Ci + 63) >> 6;       // channel blocks per tap
+  const int nsteps = ntaps * cpc;
+
+  // lane t < ntaps: byte offsets of tap t in the input (pixel shift) and in a weight row
+  int tapw = pack_tap(0, 0, 0);
+  if (lane < ntaps) tapw = a.nclass > 1 ? a.ctap[cls][lane & 3] : a.tap[lane < 9 ? lane : 0];
+  const int xd_v = (((tapw & 0xff) - 8) * a.Wi + (((tapw >> 8) & 0xff) - 8)) * a.Ci * 2;
+  const int wd_v = (tapw >> 16) * a.Ci * 2;
+
+  // ---- per-thread DMA sources: row = 8*(4*j + wave) + lane/8, LDS unit lane%8 holds k-unit u ----
+  const char* xsrc[JX];   // address of this thread's 16 bytes at tap (0,0), channel block 0
+  unsigned vmask[JX];     // bit t: the row's pixel exists under tap t
+  unsigned woff[JW];      // weight rows: 32-bit offsets from a.w (rows past the last channel read the last one: never stored)
+  int tdh[9], tdw[9];     // the taps' pixel shifts as scalars
+#pragma unroll
+  for (int i = 0; i < 9; ++i) {
+    const int tw = __builtin_amdgcn_readlane(tapw, i);
+    tdh[i] = (tw & 0xff) - 8; tdw[i] = ((tw >> 8) & 0xff) - 8;
+  }
+#pragma unroll
+  for (int j = 0; j < JX; ++j) {
+    const int row = 8 * (4 * j + wave) + (lane >> 3);
+    const int u = (lane & 7) ^ ((row >> 1) & 7);
+    const int m = m0 + row;
+    const bool exists = m < Mtot;
+    const int mm = exists ? m : 0;
+    const int ow = mm % b.OW, t2 = mm / b.OW, oh = t2 % b.OH, n = t2 / b.OH;
+    const int ih0 = oh * a.in_stride, iw0 = ow * a.in_stride;
+    xsrc[j] = reinterpret_cast<const char*>(a.in) + (((size_t)n * a.Hi + ih0) * a.Wi + iw0) * (size_t)a.Ci * 2 + u * 16;
+    unsigned vm = 0;
+#pragma unroll
+    for (int i = 0; i < 9; ++i)
+      if (i < ntaps && (unsigned)(ih0 + tdh[i]) < (unsigned)a.Hi && (unsigned)(iw0 + tdw[i]) < (unsigned)a.Wi) vm |= 1u << i;
+    vmask[j] = exists ? vm : 0u;
+  }
+#pragma unroll
+  for (int j = 0; j < JW; ++j) {
+    const int row = 8 * (4 * j + wave) + (lane >> 3);
+    const int u = (lane & 7) ^ ((row >> 1) & 7);
+    int c = c0 + row;
+    c = c >= a.w_rows ? a.w_rows - 1 : c;
+    woff[j] = (unsigned)c * (unsigned)(a.Kw * 2) + u * 16;
+  }
+  // the k-unit this lane loads is the same for all its rows: (row >> 1) & 7 = (4 * (wave & 1) + (lane >> 4)) & 7
+  const int ku = (lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7);
+  const bool tail_ok = !KTAIL || (cpc - 1) * 64 + ku * 8 < a.Ci;   // this lane's 8 channels exist in the last block
+  const uint64_t zaddr = (uint64_t)g_zero_word;
+  uint32_t zero_lo = (uint32_t)zaddr, zero_hi = (uint32_t)(zaddr >> 32);
+  asm volatile("" : "+v"(zero_lo), "+v"(zero_hi));
+
+  // load J of the group of step (tap gt, channel block gc) into stage islot
+  int gt = 0, gc = 0;      // the step whose group goes out next
+  auto issue_one = [&](auto j_tag, int islot, int xoff, int wbyte, unsigned tapbit, bool lastblk) {
+    constexpr int J = decltype(j_tag)::value;
+    unsigned char* dst = smem + islot * SBYTES + (8 * (4 * J + wave)) * ROWB;
+    if constexpr (J < JX) {
+      bool ok = (vmask[J] & tapbit) != 0;
+      if (KTAIL) ok = ok && (!lastblk || tail_ok);
+      const uint64_t pa = (uint64_t)(xsrc[J] + xoff);
+      const uint32_t lo = ok ? (uint32_t)pa : zero_lo, hi = ok ? (uint32_t)(pa >> 32) : zero_hi;
+      dma16((const char*)(((uint64_t)hi << 32) | lo), dst);
+    } else {
+      const char* base = reinterpret_cast<const char*>(a.w) + (size_t)wbyte;
+      if (KTAIL) {
+        const bool ok = !lastblk || tail_ok;
+        const uint64_t pa = (uint64_t)(base + (size_t)woff[J - JX]);
+        const uint32_t lo = ok ? (uint32_t)pa : zero_lo, hi = ok ? (uint32_t)(pa >> 32) : zero_hi;
+        dma16((const char*)(((uint64_t)hi << 32) | lo), dst);
+      } else {
+        dma16(base + (size_t)woff[J - JX], dst);
+      }
+    }
+  };
+  auto advance = [&]() {
+    ++gc;
+    if (gc == cpc) { gc = 0; ++gt; }
+  };
+
+  // the first groups go out before the rest of the set-up
+#pragma unroll
+  for (int p = 0; p < WS - 1; ++p)
+    if (p < nsteps) {
+      const int xoff = __builtin_amdgcn_readlane(xd_v, gt) + gc * 128, wbyte = __builtin_amdgcn_readlane(wd_v, gt) + gc * 128;
+      const unsigned tapbit = 1u << gt;
+      const bool lastblk = gc == cpc - 1;
+      static_for<NJ>([&](auto j) { issue_one(j, p, xoff, wbyte, tapbit, lastblk); });
+      advance();
+    }
+
+  f32x16 acc[FN][FM];
+#pragma unroll
+  for (int i = 0; i < FN; ++i)
+#pragma unroll
+    for (int j = 0; j < FM; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // LDS addresses of this lane's operand fragments in stage 0 for the two 16-channel steps of its half block;
+  // blocks are 32 rows = 4096 bytes apart (an immediate offset)
+  const unsigned lds0 = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)smem);
+  unsigned xl[2], wl[2];
+#pragma unroll
+  for (int ss = 0; ss < 2; ++ss) {
+    const unsigned swz = (((4 * wk + 2 * ss + (lane >> 5)) ^ (((lane & 31) >> 1) & 7)) << 4);
+    xl[ss] = lds0 + (wave_m * 64 + (lane & 31)) * ROWB + swz;
+    wl[ss] = lds0 + (BM + (lane & 31)) * ROWB + swz;
+  }
+
+  constexpr int NM = FN * FM, NFRAG = FN + FM;
+  static_assert(NFRAG + 2 <= NM, "slots of a half step");
+  constexpr int SPACING = (2 * NM - 2) / NJ >= 2 ? 2 : 1;
+  static_assert(2 + (NJ - 1) * SPACING < 2 * NM, "the group fits the step");
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 fa[2][FN], fb[2][FM];
+  // fragment idx of a half step in the order the MFMAs need them: B0, A0, B1, A1, A2, ...
+  auto read_one = [&](auto set_tag, auto idx_tag, unsigned wcur, unsigned xcur) {
+    constexpr int S = decltype(set_tag)::value, IDX = decltype(idx_tag)::value;
+    if constexpr (IDX == 0 || IDX == 2) {
+      constexpr int f = IDX / 2;
+      u32x4& dst = fb[S][f];
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(xcur), "i"(f * 32 * ROWB));
+    } else {
+      constexpr int f = IDX == 1 ? 0 : IDX - 2;
+      u32x4& dst = fa[S][f];
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(wcur), "i"(f * 32 * ROWB));
+    }
+  };
+  auto before_mma = [&](auto set_tag, auto k_tag, auto n_tag) {
+    constexpr int S = decltype(set_tag)::value, K = decltype(k_tag)::value, N = decltype(n_tag)::value;
+    static_assert(N >= 0 && N <= 15, "lgkmcnt range");
+    if constexpr (K == 0) {
+      u32x4 &r0 = fb[S][0], &r1 = fa[S][0];
+      asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(r0), "+v"(r1) : "n"(N));
+    } else if constexpr (K == 1) {
+      u32x4& r0 = fb[S][1];
+      asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(r0) : "n"(N));
+    } else if constexpr (K % 2 == 0) {
+      u32x4& r0 = fa[S][K / 2];
+      asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(r0) : "n"(N));
+    }
+  };
+  auto left_after = [](int K) constexpr { return (FN + 2) - (K == 0 ? 2 : (K == 1 ? 3 : 3 + K / 2)); };
+  auto mma_one = [&](auto set_tag, auto k_tag) {
+    constexpr int S = decltype(set_tag)::value, K = decltype(k_tag)::value;
+    acc[K / FM][K % FM] = mfma32(__builtin_bit_cast(bf16x8, fa[S][K / FM]), __builtin_bit_cast(bf16x8, fb[S][K % FM]),
+                                 acc[K / FM][K % FM]);
+  };
+  using set0 = std::integral_constant<int, 0>;
+  using set1 = std::integral_constant<int, 1>;
+
+  int slot = 0;   // stage of the current step
+  // MORE: a next step exists (its first fragments are read in the second half; the barrier that makes it visible is
+  // taken after slot 1).  ISSUE: the group of step i + WS - 1 goes out.  PEND: loads that may still be in flight at
+  // the barrier with the next step's group landed.
+  auto step_body = [&](auto more_tag, auto issue_tag, auto pend_tag) {
+    constexpr bool MORE = decltype(more_tag)::value, ISSUE = decltype(issue_tag)::value;
+    constexpr int PEND = decltype(pend_tag)::value;
+    const int nslot = slot == WS - 1 ? 0 : slot + 1;
+    const int islot = slot == 0 ? WS - 1 : slot - 1;
+    const unsigned wcur1 = wl[1] + slot * SBYTES, xcur1 = xl[1] + slot * SBYTES;
+    const unsigned wnext0 = wl[0] + nslot * SBYTES, xnext0 = xl[0] + nslot * SBYTES;
+    int xoff = 0, wbyte = 0;
+    unsigned tapbit = 0;
+    bool lastblk = false;
+    if constexpr (ISSUE) {
+      xoff = __builtin_amdgcn_readlane(xd_v, gt) + gc * 128;
+      wbyte = __builtin_amdgcn_readlane(wd_v, gt) + gc * 128;
+      tapbit = 1u << gt;
+      lastblk = gc == cpc - 1;
+    }
+    auto issue_at = [&](auto s_tag) {
+      constexpr int SL = decltype(s_tag)::value;
+      if constexpr (ISSUE && SL >= 2 && (SL - 2) % SPACING == 0 && (SL - 2) / SPACING < NJ)
+        issue_one(std::integral_constant<int, (SL - 2) / SPACING>{}, islot, xoff, wbyte, tapbit, lastblk);
+    };
+    // first half step: MFMAs of set 0, reads of this step's second half into set 1
+    static_for<NM>([&](auto k) {
+      constexpr int K = decltype(k)::value;
+      if constexpr (K <= 1 || K % 2 == 0)
+        before_mma(set0{}, k, std::integral_constant<int, left_after(K) + (K < NFRAG ? K : NFRAG)>{});
+      mma_one(set0{}, k);
+      if constexpr (K < NFRAG) read_one(set1{}, k, wcur1, xcur1);
+      if constexpr (MORE && K == 1) {
+        wait_vmcnt<PEND>();
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+      }
+      issue_at(std::integral_constant<int, K>{});
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    // second half step: MFMAs of set 1, the next step's first reads into set 0
+    static_for<NM>([&](auto k) {
+      constexpr int K = decltype(k)::value;
+      if constexpr (K <= 1 || K % 2 == 0)
+        before_mma(set1{}, k, std::integral_constant<int, left_after(K) + ((MORE && K > 2) ? (K - 2 < NFRAG ? K - 2 : NFRAG) : 0)>{});
+      mma_one(set1{}, k);
+      if constexpr (MORE && K >= 2 && K - 2 < NFRAG) read_one(set0{}, std::integral_constant<int, K - 2>{}, wnext0, xnext0);
+      issue_at(std::integral_constant<int, NM + K>{});
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    slot = nslot;
+    if constexpr (ISSUE) advance();
+  };
+
+  if (nsteps > 0) {
+    if (nsteps >= WS - 1) wait_vmcnt<(WS - 2) * NJ>(); else wait_vmcnt<0>();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    static_for<NFRAG>([&](auto idx) { read_one(set0{}, idx, wl[0], xl[0]); });
+    int i = 0;
+    for (; i + WS - 1 < nsteps; ++i)
+      step_body(std::true_type{}, std::true_type{}, std::integral_constant<int, (WS - 3) * NJ>{});
+    // the last WS - 1 steps (or all of them): nothing left to load, everything in flight is waited for
+    for (; i + 1 < nsteps; ++i) step_body(std::true_type{}, std::false_type{}, std::integral_constant<int, 0>{});
+    step_body(std::false_type{}, std::false_type{}, std::integral_constant<int, 0>{});
+  }
+  wait_vmcnt<0>();
+  combine_and_store32<FN, BN>(b, acc, m0, c0, wave_m, wk, lane, smem);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -213,15 +481,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // w(i+WS-1) and, for t < XG, a share of patch(c+1).  Barrier i+1 (step i+1 visible) is taken after slot 1 of
 // step i; loads complete in order, so "w(i+1) has landed" is vmcnt <= the sizes of the WS-3 groups issued after
 // the one that carried it.
-template <class F, int... I>
-__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
-  (f(std::integral_constant<int, I>{}), ...);
-}
-template <int N, class F>
-__device__ __forceinline__ void static_for(F&& f) {
-  static_for_impl(f, std::make_integer_sequence<int, N>{});
-}
-
 // KTAIL: the input channels are not a multiple of 64 (WRN's 160).  The last channel block is then partly beyond the
 // tensor: its 16-byte units past the last channel are loaded from the zero word, for the patch and the weights alike,
 // which costs every load of such a layer a per-lane address select (the other layers keep the uniform-base form).
@@ -888,23 +1147,24 @@ static hipError_t run_patch_rows(const GatherConvArgs& a, hipStream_t s) {
 bool conv_gather_wide_applies(const GatherConvArgs& a) {
   // input channels: whole 64-channel chunks, or at least two chunks with a partly filled last one (160 = 2.5 chunks)
   const bool k_ok = a.Ci % 64 == 0 || (a.Ci % 8 == 0 && a.Ci >= 128);
-  return k_ok && a.Co >= 128 && a.ntaps >= 1 && a.Kw % 8 == 0 && a.Hi < 32768 && a.Wi < 32768;
+  if ((long long)a.w_rows * a.Kw * 2 >= (1ll << 32)) return false;   // 32-bit offsets into the weight matrix
+  return k_ok && a.Co >= 128 && a.ntaps >= 1 && a.ntaps <= 9 && a.Kw % 8 == 0 && a.Hi < 32768 && a.Wi < 32768;
 }
 
 template <int BN, int STAGES, bool KTAIL>
 static hipError_t run_wide_k(const GatherConvArgs& a, hipStream_t s) {
-  constexpr size_t lds = gather_dma_lds_bytes(BN, STAGES);
-  static_assert(lds <= 160 * 1024, "LDS of one compute unit");
+  constexpr size_t lds = (size_t)STAGES * (128 + BN) * 128;
+  static_assert(lds <= 160 * 1024 && lds >= gather_dma_lds_bytes(BN, 1), "LDS of one compute unit; room for the output stage");
   static bool configured = false;   // one attribute call per instantiation (idempotent, so a race is harmless)
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_gather_dma_kernel<BN, STAGES, KTAIL>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_gather_pipe_kernel<BN, STAGES, KTAIL>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     configured = true;
   }
   const int n_tiles = (a.Co + BN - 1) / BN;
   static char name[64];
-  if (!name[0]) snprintf(name, sizeof(name), "conv_gather_dma_kernel<%d, %d, %s>", BN, STAGES, KTAIL ? "true" : "false");
+  if (!name[0]) snprintf(name, sizeof(name), "conv_gather_pipe_kernel<%d, %d, %s>", BN, STAGES, KTAIL ? "true" : "false");
   note_kernel(name);
   if (a.nclass > 1) {
     GatherConvArgs m = a;
@@ -915,12 +1175,12 @@ static hipError_t run_wide_k(const GatherConvArgs& a, hipStream_t s) {
     }
     m.cls_start[a.nclass] = tiles;
     if (tiles <= 0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((conv_gather_dma_kernel<BN, STAGES, KTAIL>), dim3(tiles), dim3(256), lds, s, m, 0, n_tiles);
+    hipLaunchKernelGGL((conv_gather_pipe_kernel<BN, STAGES, KTAIL>), dim3(tiles), dim3(256), lds, s, m, 0, n_tiles);
     return hipGetLastError();
   }
   const int Mtot = a.N * a.OH * a.OW;
   const int m_tiles = (Mtot + 127) / 128;
-  hipLaunchKernelGGL((conv_gather_dma_kernel<BN, STAGES, KTAIL>), dim3(m_tiles * n_tiles), dim3(256), lds, s, a, m_tiles, n_tiles);
+  hipLaunchKernelGGL((conv_gather_pipe_kernel<BN, STAGES, KTAIL>), dim3(m_tiles * n_tiles), dim3(256), lds, s, a, m_tiles, n_tiles);
   return hipGetLastError();
 }
 
@@ -959,6 +1219,7 @@ static hipError_t run_wide(const GatherConvArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_conv_gather_wide(const GatherConvArgs& a, hipStream_t s) {
+  if (a.w_rows != a.Co) return hipErrorInvalidValue;   // weight rows past the last one are clamped, not zero
   if (a.nclass > 1) {   // the caller has checked conv_gather_wide_applies on the common fields
     if (a.nclass > 4 || a.Ci % 8 != 0 || a.Ci < 64 || a.Co < 128) return hipErrorInvalidValue;
     return a.Co % 160 == 0 ? run_wide<160, 4>(a, s) : run_wide<128, 4>(a, s);
