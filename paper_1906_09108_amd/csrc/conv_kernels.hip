@@ -414,7 +414,8 @@ hipError_t conv_forward(const ConvShape& c, const bf16_t* x, const bf16_t* w, co
 
 static hipError_t conv_dgrad_impl(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                                   const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, stat_t* gsums, float* out_f32,
-                                  bf16_t* out_b16, hipStream_t s, bool stats_f32 = false, int rep_stride = 0);
+                                  bf16_t* out_b16, hipStream_t s, bool stats_f32 = false, int rep_stride = 0,
+                                  const bf16_t* dy2 = nullptr, const bf16_t* wt2 = nullptr);
 
 hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                       const bf16_t* addmask, float* out_f32, bf16_t* out_b16, hipStream_t s) {
@@ -459,9 +460,27 @@ hipError_t conv_dgrad_gated(const ConvShape& c, const bf16_t* dy, const bf16_t* 
   return conv_dgrad_impl(c, dy, wt, addend, nullptr, gate, bnx, gsums, out_f32, out_b16, s, false, gsums_rep_stride);
 }
 
+// the stride-2 wide path below takes both data gradients: 3x3 and 1x1 with the same stride-2 geometry and channel counts
+bool conv_dgrad_pair_applies(const ConvShape& c, const ConvShape& cp) {
+  if (c.stride != 2 || cp.stride != 2 || c.T != 9 || cp.T != 1 || c.N != cp.N || c.Hi != cp.Hi || c.Wi != cp.Wi ||
+      c.Ci != cp.Ci || c.Cip != cp.Cip || c.Co != cp.Co || c.Hi < 2 || c.Wi < 2 || c.Co % 64 != 0)
+    return false;
+  GatherConvArgs probe{};
+  probe.Hi = c.Ho(); probe.Wi = c.Wo(); probe.Ci = c.Co; probe.Co = c.Cip; probe.w_rows = c.Cip; probe.Kw = c.T * c.Co; probe.ntaps = 1;
+  return conv_gather_wide_applies(probe);
+}
+
+hipError_t conv_dgrad_gated_pair(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const ConvShape& cp, const bf16_t* dy2,
+                                 const bf16_t* wt2, const bf16_t* gate, const bf16_t* bnx, stat_t* gsums, float* out_f32,
+                                 bf16_t* out_b16, hipStream_t s, int gsums_rep_stride) {
+  if (!dy2 || !wt2 || !gate || !bnx || !gsums || !conv_dgrad_pair_applies(c, cp)) return hipErrorInvalidValue;
+  return conv_dgrad_impl(c, dy, wt, nullptr, nullptr, gate, bnx, gsums, out_f32, out_b16, s, false, gsums_rep_stride, dy2, wt2);
+}
+
 static hipError_t conv_dgrad_impl(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                                   const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, stat_t* gsums, float* out_f32,
-                                  bf16_t* out_b16, hipStream_t s, bool stats_f32, int rep_stride) {
+                                  bf16_t* out_b16, hipStream_t s, bool stats_f32, int rep_stride, const bf16_t* dy2,
+                                  const bf16_t* wt2) {
   GatherConvArgs a{};
   a.stats_rep_stride = rep_stride;
   a.in = dy; a.w = wt; a.addend = addend; a.addmask = addmask; a.out_f32 = out_f32; a.out_b16 = out_b16;
@@ -471,6 +490,7 @@ static hipError_t conv_dgrad_impl(const ConvShape& c, const bf16_t* dy, const bf
   a.OHf = c.Hi; a.OWf = c.Wi;
   a.Co = c.Cip; a.w_rows = c.Cip; a.Kw = c.T * c.Co;
   if (c.stride == 1) {
+    if (dy2) return hipErrorInvalidValue;
     // input pixel (hi, wi) receives dy[hi + 1 - r, wi + 1 - q] * w[., r, q, .]
     a.OH = c.Hi; a.OW = c.Wi; a.out_stride = 1; a.ooh = 0; a.oow = 0;
     a.ntaps = c.T;
@@ -509,11 +529,15 @@ static hipError_t conv_dgrad_impl(const ConvShape& c, const bf16_t* dy, const bf
           a.ctap[i][nt++] = pack_tap(0, 0, 0);
         }
         a.cntaps[i] = nt;
+        if (ph == 0 && pw == 0 && dy2) {   // the projection's only tap reaches the even pixels
+          a.in2 = dy2; a.w2 = wt2; a.Kw2 = c.Co; a.cls2 = i;
+        }
       }
       a.OH = a.cOH[0]; a.OW = a.cOW[0]; a.ooh = 1; a.oow = 1; a.ntaps = 0;
       return launch_conv_gather_wide(a, s);
     }
   }
+  if (dy2) return hipErrorInvalidValue;   // only the launch above adds a second data gradient
   for (int ph = 0; ph < 2; ++ph)
     for (int pw = 0; pw < 2; ++pw) {
       a.OH = (c.Hi - ph + 1) / 2; a.OW = (c.Wi - pw + 1) / 2;

@@ -245,7 +245,10 @@ __global__ __launch_bounds__(256) void conv_gather_pipe_kernel(GatherConvArgs a,
   const int m0 = (t / n_tiles) * BM, c0 = (t % n_tiles) * BN;
   const int ntaps = b.ntaps;
   const int cpc = (a.Ci + 63) >> 6;       // channel blocks per tap
-  const int nsteps = ntaps * cpc;
+  // a second source (see GatherConvArgs::in2) is one more tap, number ntaps, with pointers of its own
+  const bool has2 = a.in2 != nullptr && cls == a.cls2;
+  const int nsteps = (ntaps + (has2 ? 1 : 0)) * cpc;
+  const long long delta2 = has2 ? reinterpret_cast<const char*>(a.in2) - reinterpret_cast<const char*>(a.in) : 0;
 
   // lane t < ntaps: byte offsets of tap t in the input (pixel shift) and in a weight row
   int tapw = pack_tap(0, 0, 0);
@@ -257,6 +260,7 @@ __global__ __launch_bounds__(256) void conv_gather_pipe_kernel(GatherConvArgs a,
   const char* xsrc[JX];   // address of this thread's 16 bytes at tap (0,0), channel block 0
   unsigned vmask[JX];     // bit t: the row's pixel exists under tap t
   unsigned woff[JW];      // weight rows: 32-bit offsets from a.w (rows past the last channel read the last one: never stored)
+  unsigned woff2[JW];     // the same into a.w2
   int tdh[9], tdw[9];     // the taps' pixel shifts as scalars
 #pragma unroll
   for (int i = 0; i < 9; ++i) {
@@ -277,6 +281,7 @@ __global__ __launch_bounds__(256) void conv_gather_pipe_kernel(GatherConvArgs a,
 #pragma unroll
     for (int i = 0; i < 9; ++i)
       if (i < ntaps && (unsigned)(ih0 + tdh[i]) < (unsigned)a.Hi && (unsigned)(iw0 + tdw[i]) < (unsigned)a.Wi) vm |= 1u << i;
+    if (has2 && ih0 < a.Hi && iw0 < a.Wi) vm |= 1u << ntaps;
     vmask[j] = exists ? vm : 0u;
   }
 #pragma unroll
@@ -286,6 +291,8 @@ __global__ __launch_bounds__(256) void conv_gather_pipe_kernel(GatherConvArgs a,
     int c = c0 + row;
     c = c >= a.w_rows ? a.w_rows - 1 : c;
     woff[j] = (unsigned)c * (unsigned)(a.Kw * 2) + u * 16;
+    woff2[j] = (unsigned)c * (unsigned)(a.Kw2 * 2) + u * 16;
+    asm volatile("" : "+v"(woff[j]), "+v"(woff2[j]));   // two registers each, chosen between by a select (not a table in memory)
   }
   // the k-unit this lane loads is the same for all its rows: (row >> 1) & 7 = (4 * (wave & 1) + (lane >> 4)) & 7
   const int ku = (lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7);
@@ -296,7 +303,7 @@ __global__ __launch_bounds__(256) void conv_gather_pipe_kernel(GatherConvArgs a,
 
   // load J of the group of step (tap gt, channel block gc) into stage islot
   int gt = 0, gc = 0;      // the step whose group goes out next
-  auto issue_one = [&](auto j_tag, int islot, int xoff, int wbyte, unsigned tapbit, bool lastblk) {
+  auto issue_one = [&](auto j_tag, int islot, long long xoff, const char* wbase, bool src2, unsigned tapbit, bool lastblk) {
     constexpr int J = decltype(j_tag)::value;
     unsigned char* dst = smem + islot * SBYTES + (8 * (4 * J + wave)) * ROWB;
     if constexpr (J < JX) {
@@ -306,14 +313,15 @@ __global__ __launch_bounds__(256) void conv_gather_pipe_kernel(GatherConvArgs a,
       const uint32_t lo = ok ? (uint32_t)pa : zero_lo, hi = ok ? (uint32_t)(pa >> 32) : zero_hi;
       dma16((const char*)(((uint64_t)hi << 32) | lo), dst);
     } else {
-      const char* base = reinterpret_cast<const char*>(a.w) + (size_t)wbyte;
+      const unsigned w1 = woff[J - JX], w2 = woff2[J - JX];
+      const unsigned wo = src2 ? w2 : w1;
       if (KTAIL) {
         const bool ok = !lastblk || tail_ok;
-        const uint64_t pa = (uint64_t)(base + (size_t)woff[J - JX]);
+        const uint64_t pa = (uint64_t)(wbase + (size_t)wo);
         const uint32_t lo = ok ? (uint32_t)pa : zero_lo, hi = ok ? (uint32_t)(pa >> 32) : zero_hi;
         dma16((const char*)(((uint64_t)hi << 32) | lo), dst);
       } else {
-        dma16(base + (size_t)woff[J - JX], dst);
+        dma16(wbase + (size_t)wo, dst);
       }
     }
   };
@@ -321,15 +329,23 @@ __global__ __launch_bounds__(256) void conv_gather_pipe_kernel(GatherConvArgs a,
     ++gc;
     if (gc == cpc) { gc = 0; ++gt; }
   };
+  // where the group of step (gt, gc) reads: pixel byte offset from xsrc, weight base pointer
+  auto group_of = [&](long long& xoff, const char*& wbase, bool& src2, unsigned& tapbit, bool& lastblk) {
+    src2 = gt == ntaps;   // only reached with has2
+    xoff = (src2 ? delta2 : (long long)__builtin_amdgcn_readlane(xd_v, gt)) + gc * 128;
+    wbase = src2 ? reinterpret_cast<const char*>(a.w2) + gc * 128
+                 : reinterpret_cast<const char*>(a.w) + (__builtin_amdgcn_readlane(wd_v, gt) + gc * 128);
+    tapbit = 1u << gt;
+    lastblk = gc == cpc - 1;
+  };
 
   // the first groups go out before the rest of the set-up
 #pragma unroll
   for (int p = 0; p < WS - 1; ++p)
     if (p < nsteps) {
-      const int xoff = __builtin_amdgcn_readlane(xd_v, gt) + gc * 128, wbyte = __builtin_amdgcn_readlane(wd_v, gt) + gc * 128;
-      const unsigned tapbit = 1u << gt;
-      const bool lastblk = gc == cpc - 1;
-      static_for<NJ>([&](auto j) { issue_one(j, p, xoff, wbyte, tapbit, lastblk); });
+      long long xoff; const char* wbase; bool src2, lastblk; unsigned tapbit;
+      group_of(xoff, wbase, src2, tapbit, lastblk);
+      static_for<NJ>([&](auto j) { issue_one(j, p, xoff, wbase, src2, tapbit, lastblk); });
       advance();
     }
 
@@ -405,19 +421,15 @@ __global__ __launch_bounds__(256) void conv_gather_pipe_kernel(GatherConvArgs a,
     const int islot = slot == 0 ? WS - 1 : slot - 1;
     const unsigned wcur1 = wl[1] + slot * SBYTES, xcur1 = xl[1] + slot * SBYTES;
     const unsigned wnext0 = wl[0] + nslot * SBYTES, xnext0 = xl[0] + nslot * SBYTES;
-    int xoff = 0, wbyte = 0;
+    long long xoff = 0;
+    const char* wbase = nullptr;
     unsigned tapbit = 0;
-    bool lastblk = false;
-    if constexpr (ISSUE) {
-      xoff = __builtin_amdgcn_readlane(xd_v, gt) + gc * 128;
-      wbyte = __builtin_amdgcn_readlane(wd_v, gt) + gc * 128;
-      tapbit = 1u << gt;
-      lastblk = gc == cpc - 1;
-    }
+    bool src2 = false, lastblk = false;
+    if constexpr (ISSUE) group_of(xoff, wbase, src2, tapbit, lastblk);
     auto issue_at = [&](auto s_tag) {
       constexpr int SL = decltype(s_tag)::value;
       if constexpr (ISSUE && SL >= 2 && (SL - 2) % SPACING == 0 && (SL - 2) / SPACING < NJ)
-        issue_one(std::integral_constant<int, (SL - 2) / SPACING>{}, islot, xoff, wbyte, tapbit, lastblk);
+        issue_one(std::integral_constant<int, (SL - 2) / SPACING>{}, islot, xoff, wbase, src2, tapbit, lastblk);
     };
     // first half step: MFMAs of set 0, reads of this step's second half into set 1
     static_for<NM>([&](auto k) {

@@ -98,6 +98,13 @@ struct GatherConvArgs {
   int cls_start[5];
   int cOH[4], cOW[4], cooh[4], coow[4], cntaps[4];
   int ctap[4][4];
+  // A second contraction into the same outputs, wide pipelined kernel with nclass > 1 only: after its own taps, class
+  // cls2 also adds in2[pixel at tap (0, 0), k] * w2[c, k] over the Ci channels of in2 [N, Hi, Wi, Ci] (indexed like
+  // `in`), w2 [w_rows, Kw2].  That is the data gradient of a 1x1 stride-2 projection next to the 3x3 stride-2
+  // convolution that reads the same input.  in2 == nullptr: none.
+  const bf16_t* in2;
+  const bf16_t* w2;
+  int Kw2, cls2;
 };
 hipError_t launch_conv_gather(const GatherConvArgs& a, hipStream_t s);
 // narrow layers (16 / 32 / 64 channels in and out, 3x3, unit stride): whole patch and whole filter on chip
@@ -150,6 +157,14 @@ hipError_t conv_dgrad_feeding_next(const ConvShape& c, const bf16_t* dy, const b
                                    const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, stat_t* gsums, float* out_f32,
                                    bf16_t* out_b16, hipStream_t s, int gsums_rep_stride = 0);
 bool conv_dgrad_gates(const ConvShape& c);
+// conv_dgrad_gated of c (3x3, stride 2) with the data gradient of the 1x1 stride-2 projection cp beside it (same input
+// tensor, same output grid) added before the gate, in one launch:
+//   dx = gate > 0 ? dgrad(c; dy, wt) + dgrad(cp; dy2, wt2) : 0,  sums as conv_dgrad_gated.
+// Only where conv_dgrad_pair_applies (wide layers); hipErrorInvalidValue otherwise.
+bool conv_dgrad_pair_applies(const ConvShape& c, const ConvShape& cp);
+hipError_t conv_dgrad_gated_pair(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const ConvShape& cp, const bf16_t* dy2,
+                                 const bf16_t* wt2, const bf16_t* gate, const bf16_t* bnx, stat_t* gsums, float* out_f32,
+                                 bf16_t* out_b16, hipStream_t s, int gsums_rep_stride = 0);
 hipError_t conv_dgrad_gated(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend, const bf16_t* gate,
                             const bf16_t* bnx, stat_t* gsums, float* out_f32, bf16_t* out_b16, hipStream_t s,
                             int gsums_rep_stride = 0);

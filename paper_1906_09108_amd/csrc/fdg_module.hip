@@ -1181,9 +1181,25 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
       if (L.projects) {
         const ConvInfo& cp = p.convs[L.conv[2]];
         FDG_TRY(mconv_wgrad(m, cp, t_o1, m->GB(cur), s));
-        FDG_TRY(mconv_dgrad(m, cp, m->GB(cur), v.Wt(cp), nullptr, nullptr, m->TPB(), nullptr, s));
-        FDG_TRY(dgrad_relu_bn_backward(m, v, c1, m->T(1), v.Wt(c1), m->TPB(), b1, t_o1, in_b, m->T(0), nullptr,
-                                       need_dx ? m->G(nxt) : nullptr, need_dx ? m->GB(nxt) : nullptr, s));
+        if (conv_dgrad_pair_applies(c1.sh, cp.sh) && b1.C == c1.sh.Cip) {
+          // both data gradients into the block's input (3x3 and projection, stride 2) in one launch, gated, with the sums of BN1
+          FDG_TRY(side_wait_readers(m, m->T(0), s));
+          {
+            const double bytes = 2 * (conv_out_elems(c1.sh) + conv_out_elems(cp.sh)) + 2 * (conv_w_elems(c1.sh) + conv_w_elems(cp.sh)) +
+                                 conv_in_elems(c1.sh) * (2 + 2 + 2);
+            ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c1.sh) + conv_flops(cp.sh), bytes, s);
+            const hipError_t e = conv_dgrad_gated_pair(c1.sh, m->T(1), v.Wt(c1), cp.sh, m->GB(cur), v.Wt(cp), t_o1, in_b,
+                                                       m->bsums(b1), nullptr, m->T(0), s, p.stat_rep);
+            ps.label(c1.sh);
+            FDG_TRY(e);
+          }
+          FDG_TRY(bn_backward_after_gated_dgrad(m, v, b1, m->T(0), in_b, nullptr, need_dx ? m->G(nxt) : nullptr,
+                                                need_dx ? m->GB(nxt) : nullptr, s));
+        } else {
+          FDG_TRY(mconv_dgrad(m, cp, m->GB(cur), v.Wt(cp), nullptr, nullptr, m->TPB(), nullptr, s));
+          FDG_TRY(dgrad_relu_bn_backward(m, v, c1, m->T(1), v.Wt(c1), m->TPB(), b1, t_o1, in_b, m->T(0), nullptr,
+                                         need_dx ? m->G(nxt) : nullptr, need_dx ? m->GB(nxt) : nullptr, s));
+        }
       } else {
         FDG_TRY(dgrad_relu_bn_backward(m, v, c1, m->T(1), v.Wt(c1), nullptr, b1, t_o1, in_b, m->T(0), m->G(cur),
                                        need_dx ? m->G(nxt) : nullptr, need_dx ? m->GB(nxt) : nullptr, s));

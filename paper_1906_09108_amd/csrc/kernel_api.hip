@@ -80,6 +80,24 @@ int fdgk_conv_dgrad_gated(const void* dy_b16, const void* wt_b16, const float* a
                                static_cast<bf16_t*>(dx_b16), st(hip_stream));
 }
 
+int fdgk_conv_dgrad_pair_applies(int n, int h, int w, int ci, int co) {
+  ConvShape c, cp;
+  return conv_shape(c, n, h, w, ci, co, 3, 2) && conv_shape(cp, n, h, w, ci, co, 1, 2) && conv_dgrad_pair_applies(c, cp) ? 1 : 0;
+}
+
+int fdgk_conv_dgrad_gated_pair(const void* dy_b16, const void* wt_b16, const void* dy2_b16, const void* wt2_b16,
+                               const void* gate_b16, const void* bnx_b16, void* gsums, float* dx_f32, void* dx_b16, int n,
+                               int h, int w, int ci, int co, void* hip_stream) {
+  ConvShape c, cp;
+  if (!dy_b16 || !wt_b16 || !dy2_b16 || !wt2_b16 || !gate_b16 || !bnx_b16 || !gsums || (!dx_f32 && !dx_b16) ||
+      !conv_shape(c, n, h, w, ci, co, 3, 2) || !conv_shape(cp, n, h, w, ci, co, 1, 2))
+    return (int)hipErrorInvalidValue;
+  return (int)conv_dgrad_gated_pair(c, static_cast<const bf16_t*>(dy_b16), static_cast<const bf16_t*>(wt_b16), cp,
+                                    static_cast<const bf16_t*>(dy2_b16), static_cast<const bf16_t*>(wt2_b16),
+                                    static_cast<const bf16_t*>(gate_b16), static_cast<const bf16_t*>(bnx_b16),
+                                    static_cast<stat_t*>(gsums), dx_f32, static_cast<bf16_t*>(dx_b16), st(hip_stream));
+}
+
 int fdgk_conv_dgrad_feeding_next(const void* dy_b16, const void* wt_b16, const float* addend_f32, const void* addmask_b16,
                                  const void* gate_b16, const void* bnx_b16, void* gsums, float* dx_f32, void* dx_b16,
                                  int n, int h, int w, int ci, int co, int ksize, int stride, void* hip_stream) {

@@ -6,7 +6,7 @@ import ctypes
 
 from .binding import _ptr, _stream_handle, load
 
-KERNEL_EXPORTS = ["fdgk_conv_fwd", "fdgk_conv_dgrad", "fdgk_conv_dgrad_gated", "fdgk_conv_dgrad_feeding_next", "fdgk_conv_dgrad_gates", "fdgk_bn_bwd_gated", "fdgk_conv_wgrad", "fdgk_conv_wgrad_scratch_bytes", "fdgk_bn_stats", "fdgk_bn_apply",
+KERNEL_EXPORTS = ["fdgk_conv_fwd", "fdgk_conv_dgrad", "fdgk_conv_dgrad_gated", "fdgk_conv_dgrad_feeding_next", "fdgk_conv_dgrad_gates", "fdgk_conv_dgrad_pair_applies", "fdgk_conv_dgrad_gated_pair", "fdgk_bn_bwd_gated", "fdgk_conv_wgrad", "fdgk_conv_wgrad_scratch_bytes", "fdgk_bn_stats", "fdgk_bn_apply",
                   "fdgk_bn_bwd", "fdgk_sgd", "fdgk_bn_bwd_static", "fdgk_bn_bwd_static_max_c", "fdgk_sums_bytes", "fdgk_sums_read",
                   "fdgk_avgpool", "fdgk_fc_fwd", "fdgk_softmax_ce", "fdgk_fc_bwd", "fdgk_pool_bwd", "fdgk_nchw_to_nhwc", "fdgk_nhwc_to_nchw",
                   "fdgk_im2col7", "fdgk_maxpool3s2", "fdgk_maxpool3s2_bwd", "fdgk_dwconv3_fwd", "fdgk_dwconv3_dgrad",
@@ -24,6 +24,8 @@ def _lib():
         lib.fdgk_conv_dgrad_gated.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
         lib.fdgk_conv_dgrad_feeding_next.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
         lib.fdgk_conv_dgrad_gates.argtypes = [i, i, i, i, i, i, i]
+        lib.fdgk_conv_dgrad_pair_applies.argtypes = [i, i, i, i, i]
+        lib.fdgk_conv_dgrad_gated_pair.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, vp]
         lib.fdgk_bn_bwd_gated.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, f, vp]
         lib.fdgk_conv_wgrad.argtypes = [vp, vp, vp, vp, sz, i, i, i, i, i, i, i, i, vp]
         lib.fdgk_conv_wgrad_scratch_bytes.argtypes = [i, i, i, i, i, i, i]
@@ -102,6 +104,17 @@ def fdgk_conv_dgrad_gated(dy_b16, wt_b16, addend_f32, gate_b16, bnx_b16, gsums_f
     _ok(_lib().fdgk_conv_dgrad_gated(_ptr(dy_b16), _ptr(wt_b16), _ptr(addend_f32), _ptr(gate_b16), _ptr(bnx_b16),
                                      _ptr(gsums_f32), _ptr(dx_f32), _ptr(dx_b16), n, h, w, ci, co, ksize, stride,
                                      _stream_handle(stream)), "fdgk_conv_dgrad_gated")
+
+
+def fdgk_conv_dgrad_pair_applies(n, h, w, ci, co) -> bool:
+    return bool(_lib().fdgk_conv_dgrad_pair_applies(n, h, w, ci, co))
+
+
+def fdgk_conv_dgrad_gated_pair(dy_b16, wt_b16, dy2_b16, wt2_b16, gate_b16, bnx_b16, gsums_f32, dx_f32, dx_b16, n, h, w, ci, co,
+                               stream=None):
+    _ok(_lib().fdgk_conv_dgrad_gated_pair(_ptr(dy_b16), _ptr(wt_b16), _ptr(dy2_b16), _ptr(wt2_b16), _ptr(gate_b16), _ptr(bnx_b16),
+                                          _ptr(gsums_f32), _ptr(dx_f32), _ptr(dx_b16), n, h, w, ci, co, _stream_handle(stream)),
+        "fdgk_conv_dgrad_gated_pair")
 
 
 def fdgk_conv_dgrad_feeding_next(dy_b16, wt_b16, addend_f32, addmask_b16, gate_b16, bnx_b16, gsums_f32, dx_f32, dx_b16, n, h, w,

@@ -257,6 +257,66 @@ def test_gated_data_gradient_feeds_the_batch_norm_backward(case):
     assert rel(dx16.to(t.float32).cpu().numpy(), dref) <= B16_TOL
 
 
+PAIR_CASES = [  # (n, h, w, ci, co): 3x3 stride-2 layer with a 1x1 stride-2 projection beside it
+    (2, 8, 8, 128, 128),
+    (3, 9, 7, 192, 320),       # odd sizes: parity classes of different extent, ragged pixel tiles
+    (16, 16, 16, 320, 640),    # WRN-28-10's second transition at a reduced batch: several tiles per class
+    (2, 6, 6, 160, 192),       # 160 output channels of the data gradient: one ragged 160-wide tile
+]
+
+
+@pytest.mark.parametrize("case", PAIR_CASES)
+def test_gated_data_gradient_of_a_projecting_block(case):
+    """conv_dgrad_gated_pair = gate > 0 ? dgrad of the 3x3 stride-2 convolution + dgrad of the 1x1 stride-2 projection : 0,
+    with the sums of its bf16 values.  Reference: the oracle's two data gradients added, gated in numpy."""
+    from paper_1906_09108_amd import kernels as K
+    t = _torch()
+    n, h, w, ci, co = case
+    print("gated dgrad pair", case, flush=True)
+    assert K.fdgk_conv_dgrad_pair_applies(n, h, w, ci, co)
+    x_unused, wt, dy, ho, wo = _conv_data((n, h, w, ci, co, 3, 2), 21)
+    _, wt2, dy2, ho2, wo2 = _conv_data((n, h, w, ci, co, 1, 2), 22)
+    assert (ho, wo) == (ho2, wo2)
+    r = np.random.default_rng(23)
+    ref = (K32.conv_bwd_data(dy, wt, x_unused.shape, 2, 1).astype(np.float64) +
+           K32.conv_bwd_data(dy2, wt2, x_unused.shape, 2, 0).astype(np.float64))
+    gate = bf16_round(np.maximum(r.standard_normal(ref.shape), 0))
+    bnx = bf16_round(r.standard_normal(ref.shape) * (0.5 + r.random((1, ci, 1, 1))) + r.standard_normal((1, ci, 1, 1)))
+    wtd = t.from_numpy(wt.transpose(1, 2, 3, 0).copy()).to(t.bfloat16).contiguous().cuda()
+    wtd2 = t.from_numpy(wt2.transpose(1, 2, 3, 0).copy()).to(t.bfloat16).contiguous().cuda()
+    gsums = K.new_sums(ci)
+    g32 = t.full((n, h, w, ci), float("nan"), dtype=t.float32, device="cuda")
+    g16 = t.zeros((n, h, w, ci), dtype=t.bfloat16, device="cuda")
+    K.fdgk_conv_dgrad_gated_pair(to_dev_nhwc_b16(dy), wtd, to_dev_nhwc_b16(dy2), wtd2, to_dev_nhwc_b16(gate), to_dev_nhwc_b16(bnx),
+                                 gsums, g32, g16, n, h, w, ci, co)
+    t.cuda.synchronize()
+    g_ref = ref * (gate > 0)
+    assert rel(nhwc_to_nchw(g32), g_ref) <= F32_TOL
+    assert rel(nhwc_to_nchw(g16), g_ref) <= B16_TOL
+    assert np.all(nhwc_to_nchw(g32)[gate <= 0] == 0)
+    # the projection reaches the even pixels only: elsewhere the result is the 3x3 data gradient alone
+    only3 = K32.conv_bwd_data(dy, wt, x_unused.shape, 2, 1).astype(np.float64) * (gate > 0)
+    odd = np.ones((h, w), bool)
+    odd[::2, ::2] = False
+    assert rel(nhwc_to_nchw(g32)[:, :, odd], only3[:, :, odd]) <= F32_TOL
+    gb = g16.to(t.float64).reshape(-1, ci).cpu().numpy()
+    xb = to_dev_nhwc_b16(bnx).to(t.float64).reshape(-1, ci).cpu().numpy()
+    got = K.fdgk_sums_read(gsums, ci)
+    assert rel(got[:ci], gb.sum(0)) <= 1e-5
+    assert rel(got[ci:], (gb * xb).sum(0)) <= 1e-5
+
+
+def test_gated_pair_refuses_what_it_does_not_cover():
+    from paper_1906_09108_amd import kernels as K
+    t = _torch()
+    assert not K.fdgk_conv_dgrad_pair_applies(2, 8, 8, 32, 64)     # narrow layer
+    assert not K.fdgk_conv_dgrad_pair_applies(2, 1, 1, 128, 128)   # a single pixel
+    z = t.zeros(16, dtype=t.bfloat16, device="cuda")
+    st = K.new_sums(32)
+    with pytest.raises(RuntimeError):
+        K.fdgk_conv_dgrad_gated_pair(z, z, z, z, z, z, st, None, z, 2, 8, 8, 32, 64)
+
+
 @pytest.mark.parametrize("case", [(3, 7, 5, 16, 16, 3, 1), (16, 32, 32, 16, 16, 3, 1), (4, 16, 16, 32, 32, 3, 1), (3, 8, 8, 64, 64, 3, 1),
                                   (9, 64, 64, 64, 64, 3, 1),
                                   (25, 14, 14, 1024, 256, 1, 1)])   # 1x1 of a bottleneck block: the two-workgroup wide kernel
