@@ -53,13 +53,15 @@ def measured_traffic(config: int, kernel: str):
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)     # about half a second of the headline step: the clock under load has settled
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..10 (default 4: WRN-28-10 top module)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--two-streams", action="store_true",
-                    help="forward on one stream, delayed backward + update on another (modules with delay >= 1: the two touch "
-                         "different saved forwards and overlap on the GPU)")
+                    help="forward on one stream, delayed backward + update on another: the default for modules with delay >= 1 "
+                         "in the stored form (the two touch different saved forwards and overlap on the GPU: the decoupling "
+                         "the method is about); an error where it does not apply")
+    ap.add_argument("--one-stream", action="store_true", help="everything on one stream also where the delay is >= 1")
     ap.add_argument("--graph", action="store_true",
                     help="record the step into HIP graphs (one per position of the history ring) and time their replay")
     ap.add_argument("--replay", action="store_true",
@@ -218,7 +220,7 @@ def main():
     for t in range(spec.delay):                       # fill the history ring
         mod.forward(xs[t % pool], labels[t % pool], y, stream)
 
-    two = bool(args.two_streams)
+    two = bool(args.two_streams) or (spec.delay >= 1 and not args.replay and not args.graph and not args.one_stream)
     if two and (spec.delay < 1 or args.replay):
         print("--two-streams needs a module with delay >= 1 in the stored form", file=sys.stderr)
         sys.exit(2)
@@ -230,6 +232,11 @@ def main():
         ev_fwd, ev_upd = torch.cuda.Event(), torch.cuda.Event()
         torch.cuda.synchronize()
         ev_upd.record(s_bwd)
+
+    def step_one(i):
+        mod.forward(xs[i % pool], labels[i % pool], y, stream)
+        mod.backward_delayed(gs[i % pool], grad_in, stream)
+        mod.update(lr, stream)
 
     def step(i):
         if two:
@@ -248,7 +255,6 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    eager_step = step
     if args.graph:
         # One graph per ring position (the slot pointers of a step are fixed in it); the replays continue the cycle
         # the recording went through.  The library allocates nothing, clears memory with kernels (no memset nodes)
@@ -282,10 +288,11 @@ def main():
         print("non-finite module output", file=sys.stderr)
         sys.exit(1)
 
-    # second pass over the same number of steps with per-class HIP events (eager: the profiler's events are not
-    # part of a recorded graph)
-    step = eager_step
+    # second pass (at most 40 steps) with per-class HIP events (eager: the profiler's events are not part of a
+    # recorded graph)
+    step = step_one         # per-kernel times are taken with everything on one stream: a kernel's time is then its own
     torch.cuda.synchronize()
+    prof_steps = min(args.steps, 40)
     if args.graph:
         # The replays advanced the ring on the device while the library's host counters stayed where the recording
         # left them: an eager step of THIS module would pop a slot that is not the oldest saved forward.  The
@@ -300,7 +307,7 @@ def main():
             step(i)
         torch.cuda.synchronize()
     mod.profile_enable(True)
-    for i in range(args.steps):
+    for i in range(prof_steps):
         step(args.warmup + args.steps + i)
     entries = mod.profile_read()
     mod.profile_enable(False)
@@ -328,16 +335,16 @@ def main():
         achieved = dom["bytes"] / dom["calls"] / (avg_ms * 1e-3) / 1e9
         roofline = {"kernel": name, "bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": achieved / PEAK_HBM_GBS}
-    roofline.update({"avg_launch_ms": avg_ms, "calls_per_step": dom["calls"] / args.steps,
+    roofline.update({"avg_launch_ms": avg_ms, "calls_per_step": dom["calls"] / prof_steps,
                      "share_of_step": dom["total_ms"] / total_ms,
                      "algorithmic_flops_per_launch": dom["flops"] / dom["calls"],
                      "algorithmic_bytes_per_launch": dom["bytes"] / dom["calls"]})
     roofline["traffic"], roofline["traffic_source"] = measured_traffic(args.config, name)
-    classes = {k: {"ms_per_step": v["total_ms"] / args.steps, "calls_per_step": v["calls"] / args.steps,
+    classes = {k: {"ms_per_step": v["total_ms"] / prof_steps, "calls_per_step": v["calls"] / prof_steps,
                    "TFLOP/s": (v["flops"] / (v["total_ms"] * 1e-3) / 1e12) if v["flops"] else None,
                    "GB/s": v["bytes"] / (v["total_ms"] * 1e-3) / 1e9}
                for k, v in sorted(prof.items(), key=lambda kv: -kv[1]["total_ms"])}
-    per_kernel = {k: {"ms_per_step": v["total_ms"] / args.steps, "calls_per_step": v["calls"] / args.steps,
+    per_kernel = {k: {"ms_per_step": v["total_ms"] / prof_steps, "calls_per_step": v["calls"] / prof_steps,
                       "avg_us": 1e3 * v["total_ms"] / v["calls"],
                       "TFLOP/s": (v["flops"] / (v["total_ms"] * 1e-3) / 1e12) if v["flops"] else None}
                   for k, v in sorted(kernels.items(), key=lambda kv: -kv[1]["total_ms"]) if v["flops"]}
@@ -350,8 +357,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": spec.name, "batch": spec.n, "delay": spec.delay, "beta": spec.beta,
                    "saved_forward": "input + weight snapshot, replayed by the backward" if args.replay else "activations",
-                   "streams": "forward on one, delayed backward + update on another" if args.two_streams else "one",
-                   "launch": "HIP graph replay" if args.graph else "eager",
+                   "streams": "forward on one, delayed backward + update on another" if two else "one",
+                   "launch": "HIP graph replay" if args.graph else "eager", "profiled_steps": prof_steps,
                    "workspace_MiB": mod.workspace_bytes / 2 ** 20,
                    "params": W.param_count(spec), "useful_conv_gflop_per_step": W.conv_flops(spec) / 1e9},
         "step_tflops": W.conv_flops(spec) / (ms_per_step * 1e-3) / 1e12,
