@@ -393,8 +393,8 @@ hipError_t launch_conv_wgrad(const WgradArgs& a, hipStream_t s) {
 // ------------------------------------------------------------------------------------------------
 // geometry of the three passes of one convolution
 // ------------------------------------------------------------------------------------------------
-hipError_t conv_forward(const ConvShape& c, const bf16_t* x, const bf16_t* w, const float* addend, float* out_f32,
-                        bf16_t* out_b16, stat_t* stats, hipStream_t s, int stats_rep_stride) {
+static GatherConvArgs forward_args(const ConvShape& c, const bf16_t* x, const bf16_t* w, const float* addend, float* out_f32,
+                                   bf16_t* out_b16, stat_t* stats, int stats_rep_stride) {
   GatherConvArgs a{};
   a.stats_rep_stride = stats_rep_stride;
   a.in = x; a.w = w; a.addend = addend; a.addmask = nullptr; a.out_f32 = out_f32; a.out_b16 = out_b16; a.stats = stats;
@@ -409,7 +409,27 @@ hipError_t conv_forward(const ConvShape& c, const bf16_t* x, const bf16_t* w, co
   } else {
     a.tap[0] = pack_tap(0, 0, 0);
   }
-  return launch_conv_gather(a, s);
+  return a;
+}
+
+hipError_t conv_forward(const ConvShape& c, const bf16_t* x, const bf16_t* w, const float* addend, float* out_f32,
+                        bf16_t* out_b16, stat_t* stats, hipStream_t s, int stats_rep_stride) {
+  return launch_conv_gather(forward_args(c, x, w, addend, out_f32, out_b16, stats, stats_rep_stride), s);
+}
+
+bool conv_forward_bn_applies(const ConvShape& c) {
+  if (c.Ci != c.Cip) return false;
+  return conv_narrow_transforms(forward_args(c, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0), false, false);
+}
+
+hipError_t conv_forward_bn(const ConvShape& c, const ConvInputBn& bn, const bf16_t* w, const float* addend, float* out_f32,
+                           bf16_t* out_b16, stat_t* stats, hipStream_t s, int stats_rep_stride) {
+  if (!bn.x_raw || !bn.sums || !bn.gamma || !bn.beta || !bn.act_out || !conv_forward_bn_applies(c)) return hipErrorInvalidValue;
+  GatherConvArgs a = forward_args(c, nullptr, w, addend, out_f32, out_b16, stats, stats_rep_stride);
+  a.tr_mode = 1; a.tr_p = bn.x_raw; a.tr_out = bn.act_out; a.tr_sums = bn.sums; a.tr_gamma = bn.gamma; a.tr_beta = bn.beta;
+  a.tr_run_mean = bn.run_mean; a.tr_run_var = bn.run_mean ? bn.run_var : nullptr;
+  a.tr_eps = bn.eps; a.tr_momentum = bn.momentum; a.tr_rep_stride = bn.rep_stride;
+  return launch_conv_narrow(a, s);
 }
 
 static hipError_t conv_dgrad_impl(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,

@@ -327,6 +327,282 @@ hipError_t run_narrow_j(const GatherConvArgs& a, hipStream_t s) {
   return run_narrow<CI, NB, WN, 1>(a, s);
 }
 
+// ------------------------------------------------------------------------------------------------
+// The same with an input transform (GatherConvArgs::tr_mode): the batch-norm pass that would precede the
+// convolution -- forward batch norm + ReLU, or the apply half of a batch-norm backward -- runs on the patch in LDS.
+// ------------------------------------------------------------------------------------------------
+// A narrow layer's launch is a chain of dependent round trips, and so is the batch-norm pass before it: fused, the
+// pass costs one more trip through LDS instead of a launch.  The workgroup lands the RAW patches (p, and q in mode 2)
+// beside the convolution's patch buffer, works out the per-channel coefficients from the exact sums while those
+// loads are in flight (thread c < CI: channel c; a table in LDS), then every thread turns its units of the patch:
+// y = act(A p + B q + C), rounded to bf16, written where the convolution reads it (same rows, same unit swizzle) and,
+// for the pixels of the workgroup's own tile, to tr_out in global memory -- the tensor the backward (or the weight
+// gradient) reads later.  Halo rows are transformed by every workgroup that needs them; the zero area stays zero, so
+// padding is zero AFTER the transform, as it must be.  One tile per workgroup; the rest (filter in registers, MFMAs,
+// output stage) is conv_narrow_kernel's.
+template <int CI, int NB, int WN, int J, bool PF32, bool WQ>
+__global__ __launch_bounds__(256) void conv_narrow_tr_kernel(GatherConvArgs a, NarrowLaunch L) {
+  constexpr int WM = 4 / WN, TP = 16 * J * WM, CO = 16 * NB * WN;
+  constexpr int U = CI / 8, ROWB = CI * 2;
+  constexpr int S = (9 * CI + 31) / 32;
+  constexpr int SWZ_SHIFT = U == 2 ? 2 : (U == 4 ? 1 : 0);
+  constexpr int UP = PF32 ? 2 * U : U;                 // 16-byte units of one pixel of p
+  static_assert(CI == 16 || CI == 32 || CI == 64, "real input channels");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave % WM, wn = wave / WM;
+  const int W = a.Wi, H = a.Hi;
+  const int Mtot = a.N * H * W;
+  const int units = L.units;
+  const int tile = narrow_xcd_consecutive(blockIdx.x, gridDim.x);
+  const int m0 = tile * TP;
+
+  unsigned char* patch = smem;                                   // units * 16, then 128 bytes of zeros
+  float* coef = reinterpret_cast<float*>(smem + (size_t)units * 16 + 128);   // A[CI], B[CI], C[CI]
+  unsigned char* rawp = reinterpret_cast<unsigned char*>(coef + 3 * CI);
+  unsigned char* rawq = rawp + (size_t)units * (PF32 ? 32 : 16);
+  if (tid < 8) reinterpret_cast<uint4*>(patch + (size_t)units * 16)[tid] = make_uint4(0u, 0u, 0u, 0u);
+
+  // ---- the raw patches: row r holds pixel m0 - W - 1 + r (rows that do not exist read some row that does) ----
+  {
+    const int units_p = units * (PF32 ? 2 : 1);
+    for (int base = wave * 64; base < units_p; base += 256) {
+      const int pos = base + lane;
+      const int r = pos / UP, up = pos % UP;
+      int q = m0 - W - 1 + r;
+      q = q < 0 ? 0 : (q >= Mtot ? Mtot - 1 : q);
+      narrow_dma16(reinterpret_cast<const char*>(a.tr_p) + (size_t)q * (CI * (PF32 ? 4 : 2)) + up * 16, rawp + (size_t)base * 16);
+    }
+    if (WQ) {
+      for (int base = wave * 64; base < units; base += 256) {
+        const int pos = base + lane;
+        const int r = pos / U, uq = pos % U;
+        int q = m0 - W - 1 + r;
+        q = q < 0 ? 0 : (q >= Mtot ? Mtot - 1 : q);
+        narrow_dma16(reinterpret_cast<const char*>(a.tr_q) + (size_t)q * ROWB + uq * 16, rawq + (size_t)base * 16);
+      }
+    }
+  }
+
+  // ---- the filter (as conv_narrow_kernel) ----
+  bf16x8 wf[S][NB];
+  {
+    const int g = lane >> 4;
+#pragma unroll
+    for (int s = 0; s < S; ++s)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const int co = (wn * NB + nb) * 16 + (lane & 15);
+        const int k = 32 * s + 8 * g;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (k < 9 * CI && co < a.w_rows) v = *reinterpret_cast<const uint4*>(a.w + (size_t)co * a.Kw + k);
+        wf[s][nb] = __builtin_bit_cast(bf16x8, v);
+      }
+  }
+
+  // ---- per-channel coefficients from the exact sums (the same expressions as the batch-norm kernels).  Eight lanes per
+  //      channel, one per copy of the sums: all words are requested at once (taken copy after copy by one thread they
+  //      are seven dependent trips to memory), the integer words are added across the lanes, lane 0 of the eight works
+  //      out the channel's constants ----
+  for (int t0 = 0; t0 < 8 * CI; t0 += 256) {
+    const int t = t0 + tid;                    // 8 * CI is a multiple of 64: whole waves take part in the shuffles
+    if (t0 + (tid & ~63) >= 8 * CI) break;
+    const int c = t >> 3, rp = t & 7, rep = a.tr_rep_stride;
+    const bool has = rep > 0 || rp == 0;       // a single copy: only the first lane reads
+    auto total = [&](const stat_t* stats, int which) {
+      const stat_t* q = stats + (size_t)which * CI + c + (size_t)(rep > 0 ? rp : 0) * rep;
+      long long hi = has ? q[0] : 0, lo = has ? q[2 * (size_t)CI] : 0;
+      double big = has ? __builtin_bit_cast(double, q[4 * (size_t)CI]) : 0.0;
+#pragma unroll
+      for (int off = 1; off < 8; off <<= 1) {
+        hi += __shfl_xor(hi, off);
+        lo += __shfl_xor(lo, off);
+        big += __shfl_xor(big, off);
+      }
+      return stat_value(hi, lo, __builtin_bit_cast(long long, big));
+    };
+    const double s1 = total(a.tr_sums, 0), s2 = total(a.tr_sums, 1);
+    double t1 = 0.0, t2 = 0.0;
+    if (WQ) { t1 = total(a.tr_bsums, 0); t2 = total(a.tr_bsums, 1); }
+    if (rp != 0) continue;
+    const double invMd = 1.0 / (double)Mtot;
+    const double md = s1 * invMd;
+    const double var = fmax(s2 * invMd - md * md, 0.0);
+    const float mean = (float)md, is = rsqrtf((float)var + a.tr_eps);
+    const float g = a.tr_gamma[c] * is;
+    float A = g, B = 0.f, C;
+    if (!WQ) {
+      C = a.tr_beta[c] - mean * g;
+      if (blockIdx.x == 0 && a.tr_run_mean) {
+        const float unbias = Mtot > 1 ? (float)Mtot / (float)(Mtot - 1) : 1.f, mom = a.tr_momentum;
+        a.tr_run_mean[c] = (1.f - mom) * a.tr_run_mean[c] + mom * mean;
+        a.tr_run_var[c] = (1.f - mom) * a.tr_run_var[c] + mom * (float)var * unbias;
+      }
+    } else {
+      const float invM = (float)invMd;
+      const float b1 = (float)t1;
+      const float b2 = is * (float)(t2 - md * t1);     // sum g*xhat from sum g*x and sum g, the difference in double
+      const float k1 = b1 * invM, k2 = b2 * invM;
+      B = -g * k2 * is;
+      C = -g * k1 + g * k2 * is * mean;
+      if (blockIdx.x == 0) {
+        a.tr_dbeta[c] = b1;
+        a.tr_dgamma[c] = b2;
+      }
+    }
+    coef[c] = A; coef[CI + c] = B; coef[2 * CI + c] = C;
+  }
+
+  // ---- LDS address of this lane's pixel fragment for every pixel block and step (as conv_narrow_kernel) ----
+  constexpr int SA = CI == 64 ? 9 : S;
+  const unsigned zero_addr = (unsigned)units * 16u;
+  unsigned xaddr[J][SA];
+  {
+    const int g = lane >> 4;
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+      const int pl = (wm * J + j) * 16 + (lane & 15);
+      const int m = m0 + pl;
+      const bool inside = m < Mtot;
+      const int row = narrow_div(m, L.magic_w), ow = m - row * W;
+      const int oh = row - narrow_div(row, L.magic_h) * H;
+#pragma unroll
+      for (int s = 0; s < SA; ++s) {
+        const int slot = CI == 16 ? 2 * s + (g >> 1) : s;
+        const int u = CI == 16 ? (g & 1) : g;
+        unsigned addr = zero_addr;
+        if (slot < 9) {
+          const int tp = a.tap[slot];
+          const int dh = (tp & 0xff) - 8, dw = ((tp >> 8) & 0xff) - 8;
+          const bool ok = inside && (unsigned)(oh + dh) < (unsigned)H && (unsigned)(ow + dw) < (unsigned)W;
+          const int r = pl + W + 1 + dh * W + dw;
+          if (ok) addr = (unsigned)(r * ROWB + ((u ^ ((r >> SWZ_SHIFT) & (U - 1))) << 4));
+        }
+        xaddr[j][s] = addr;
+      }
+    }
+  }
+
+  __builtin_amdgcn_s_waitcnt(0);   // this wave's loads have landed (raw patches in LDS, filter in registers)
+  __syncthreads();                 // ... and every wave's; the coefficient table is written
+
+  // ---- the transform: conv-patch unit `pos` = row pos / U, stored unit pos % U holding channel unit u ----
+  for (int pos = tid; pos < units; pos += 256) {
+    const int r = pos / U, us = pos % U;
+    const int u = us ^ ((r >> SWZ_SHIFT) & (U - 1));
+    float pv[8], y[8];
+    if (PF32) {
+      const float4 lo = *reinterpret_cast<const float4*>(rawp + ((size_t)r * UP + 2 * u) * 16);
+      const float4 hi = *reinterpret_cast<const float4*>(rawp + ((size_t)r * UP + 2 * u + 1) * 16);
+      pv[0] = lo.x; pv[1] = lo.y; pv[2] = lo.z; pv[3] = lo.w; pv[4] = hi.x; pv[5] = hi.y; pv[6] = hi.z; pv[7] = hi.w;
+    } else {
+      const uint4 v = *reinterpret_cast<const uint4*>(rawp + ((size_t)r * UP + u) * 16);
+      pv[0] = bf16_lo(v.x); pv[1] = bf16_hi(v.x); pv[2] = bf16_lo(v.y); pv[3] = bf16_hi(v.y);
+      pv[4] = bf16_lo(v.z); pv[5] = bf16_hi(v.z); pv[6] = bf16_lo(v.w); pv[7] = bf16_hi(v.w);
+    }
+    const float4 A0 = *reinterpret_cast<const float4*>(coef + 8 * u), A1 = *reinterpret_cast<const float4*>(coef + 8 * u + 4);
+    const float4 C0 = *reinterpret_cast<const float4*>(coef + 2 * CI + 8 * u), C1 = *reinterpret_cast<const float4*>(coef + 2 * CI + 8 * u + 4);
+    const float Av[8] = {A0.x, A0.y, A0.z, A0.w, A1.x, A1.y, A1.z, A1.w};
+    const float Cv[8] = {C0.x, C0.y, C0.z, C0.w, C1.x, C1.y, C1.z, C1.w};
+    if (WQ) {
+      const uint4 v = *reinterpret_cast<const uint4*>(rawq + ((size_t)r * U + u) * 16);
+      const float qv[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y), bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
+      const float4 B0 = *reinterpret_cast<const float4*>(coef + CI + 8 * u), B1 = *reinterpret_cast<const float4*>(coef + CI + 8 * u + 4);
+      const float Bv[8] = {B0.x, B0.y, B0.z, B0.w, B1.x, B1.y, B1.z, B1.w};
+#pragma unroll
+      for (int i = 0; i < 8; ++i) y[i] = Av[i] * pv[i] + (Bv[i] * qv[i] + Cv[i]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) y[i] = fmaxf(pv[i] * Av[i] + Cv[i], 0.f);
+    }
+    const uint4 packed = make_uint4(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]), pack_bf16x2(y[6], y[7]));
+    *reinterpret_cast<uint4*>(patch + (size_t)pos * 16) = packed;
+    const int pl = r - (W + 1);
+    if (pl >= 0 && pl < TP && m0 + pl < Mtot)
+      *reinterpret_cast<uint4*>(a.tr_out + (size_t)(m0 + pl) * CI + 8 * u) = packed;
+  }
+  __syncthreads();
+
+  f32x4 acc[NB][J];
+#pragma unroll
+  for (int i = 0; i < NB; ++i)
+#pragma unroll
+    for (int j = 0; j < J; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int j = 0; j < J; ++j)
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+      const unsigned addr = CI == 64 ? (xaddr[j][s >> 1] ^ ((s & 1) << 6)) : xaddr[j][s];
+      const bf16x8 b = *reinterpret_cast<const bf16x8*>(patch + addr);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) acc[nb][j] = mfma16(wf[s][nb], b, acc[nb][j]);
+    }
+
+  float s1[NB][4], s2[NB][4];
+#pragma unroll
+  for (int i = 0; i < NB; ++i)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) s1[i][v] = s2[i][v] = 0.f;
+  narrow_store<J, NB, WN, CO>(a, acc, m0 + wm * J * 16, wave, lane, Mtot, s1, s2);
+  narrow_flush_sums<NB, WN, CO>(a, s1, s2, wave, lane);
+}
+
+// LDS of the kernel above for `units` units of patch
+static size_t narrow_tr_lds(int units, int CI, bool p_f32, bool with_q) {
+  return (size_t)units * 16 + 128 + (size_t)12 * CI + (size_t)units * (p_f32 ? 32 : 16) + (with_q ? (size_t)units * 16 : 0);
+}
+constexpr int kNarrowTrMaxTiles = 1024;   // beyond that a workgroup per tile re-reads the filter too often: the looped kernel runs
+constexpr size_t kNarrowTrMaxLds = 150 * 1024;
+
+template <int CI, int NB, int WN, int J, bool PF32, bool WQ>
+hipError_t run_narrow_tr(const GatherConvArgs& a, hipStream_t s) {
+  constexpr int WM = 4 / WN, TP = 16 * J * WM, U = CI / 8;
+  const int Mtot = a.N * a.OH * a.OW;
+  const int rows = TP + 2 * a.Wi + 2;
+  const int units = (rows * U + 255) / 256 * 256;
+  const size_t lds = narrow_tr_lds(units, CI, PF32, WQ);
+  const int ntiles = (Mtot + TP - 1) / TP;
+  if (lds > kNarrowTrMaxLds || ntiles > kNarrowTrMaxTiles) return hipErrorInvalidValue;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_narrow_tr_kernel<CI, NB, WN, J, PF32, WQ>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kNarrowTrMaxLds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  static char name[80];
+  if (!name[0]) snprintf(name, sizeof(name), "conv_narrow_tr_kernel<%d, %d, %d, %d, %s>", CI, NB, WN, J, WQ ? (PF32 ? "bn bwd f32" : "bn bwd") : "bn fwd");
+  note_kernel(name);
+  NarrowLaunch L;
+  L.units = units;
+  L.magic_w = ((1ull << 40) + a.Wi - 1) / a.Wi;
+  L.magic_h = ((1ull << 40) + a.Hi - 1) / a.Hi;
+  L.same_masks = 0;
+  hipLaunchKernelGGL((conv_narrow_tr_kernel<CI, NB, WN, J, PF32, WQ>), dim3(ntiles), dim3(256), lds, s, a, L);
+  return hipGetLastError();
+}
+
+// pixel blocks per wave as run_narrow_j
+template <int WM>
+static int narrow_j_for(int Mtot) { return Mtot >= 512 * 64 * WM ? 4 : (Mtot >= 512 * 32 * WM ? 2 : 1); }
+
+template <int CI, int NB, int WN, bool PF32, bool WQ>
+hipError_t run_narrow_tr_j(const GatherConvArgs& a, hipStream_t s) {
+  switch (narrow_j_for<4 / WN>(a.N * a.OH * a.OW)) {
+    case 4: return run_narrow_tr<CI, NB, WN, 4, PF32, WQ>(a, s);
+    case 2: return run_narrow_tr<CI, NB, WN, 2, PF32, WQ>(a, s);
+    default: return run_narrow_tr<CI, NB, WN, 1, PF32, WQ>(a, s);
+  }
+}
+template <bool PF32, bool WQ>
+hipError_t run_narrow_tr_c(const GatherConvArgs& a, hipStream_t s) {
+  if (a.Ci == 16) return run_narrow_tr_j<16, 1, 1, PF32, WQ>(a, s);
+  if (a.Ci == 32) return run_narrow_tr_j<32, 2, 1, PF32, WQ>(a, s);
+  return run_narrow_tr_j<64, 2, 2, PF32, WQ>(a, s);
+}
+
 
 // ------------------------------------------------------------------------------------------------
 // Weight gradient of the same layers: dw[co, tap, ci] = sum over pixels of dy[pixel, co] * x[pixel + tap, ci]
@@ -572,8 +848,26 @@ bool conv_narrow_applies(const GatherConvArgs& a) {
   return true;
 }
 
+bool conv_narrow_transforms(const GatherConvArgs& a, bool p_f32, bool with_q) {
+  if (!conv_narrow_applies(a) || (a.Ci != 16 && a.Ci != 32 && a.Ci != 64)) return false;
+  const int Mtot = a.N * a.OH * a.OW;
+  const int WM = a.Ci == 64 ? 2 : 4;
+  const int J = Mtot >= 512 * 64 * WM ? 4 : (Mtot >= 512 * 32 * WM ? 2 : 1);
+  const int TP = 16 * J * WM;
+  const int units = ((TP + 2 * a.Wi + 2) * (a.Ci / 8) + 255) / 256 * 256;
+  return Mtot > 0 && (Mtot + TP - 1) / TP <= kNarrowTrMaxTiles && narrow_tr_lds(units, a.Ci, p_f32, with_q) <= kNarrowTrMaxLds;
+}
+
 hipError_t launch_conv_narrow(const GatherConvArgs& a, hipStream_t s) {
   if (!conv_narrow_applies(a) || a.N * a.OH * a.OW <= 0) return hipErrorInvalidValue;
+  if (a.tr_mode != 0) {
+    const bool wq = a.tr_mode == 2;
+    if ((a.tr_mode != 1 && a.tr_mode != 2) || !a.tr_p || !a.tr_out || !a.tr_sums || !a.tr_gamma || (wq && (!a.tr_q || !a.tr_bsums || !a.tr_dgamma || !a.tr_dbeta)) ||
+        (!wq && (!a.tr_beta || a.tr_p_f32)) || !conv_narrow_transforms(a, a.tr_p_f32 != 0, wq))
+      return hipErrorInvalidValue;
+    if (!wq) return run_narrow_tr_c<false, false>(a, s);
+    return a.tr_p_f32 ? run_narrow_tr_c<true, true>(a, s) : run_narrow_tr_c<false, true>(a, s);
+  }
   if (a.Ci == 8) return a.Co == 16 ? run_narrow_j<8, 1, 1>(a, s) : (a.Co == 32 ? run_narrow_j<8, 2, 1>(a, s) : run_narrow_j<8, 4, 1>(a, s));
   if (a.Ci == 16) return run_narrow_j<16, 1, 1>(a, s);
   if (a.Ci == 32) return run_narrow_j<32, 2, 1>(a, s);

@@ -105,7 +105,34 @@ struct GatherConvArgs {
   const bf16_t* in2;
   const bf16_t* w2;
   int Kw2, cls2;
+  // Input transform, narrow kernel only (tr_mode != 0; `in` is not read): the convolution's input is
+  //   y = act(A[c] * p + B[c] * q + C[c]), rounded to bf16,
+  // worked out in LDS from the raw patches of p (tr_p: bf16, or fp32 with tr_p_f32) and q (tr_q, bf16, mode 2 only),
+  // both [N, Hi, Wi, Ci], with per-channel coefficients from batch-norm sums; every workgroup also writes the y of its
+  // own pixels to tr_out (bf16 [N, Hi, Wi, Ci]), which is then what a batch-norm pass of its own would have left.
+  //   mode 1: forward batch norm + ReLU of p.  A = gamma * invstd, B = 0, C = beta - mean * A from tr_sums (sums of p);
+  //           act = max(., 0); tr_run_mean / tr_run_var (optional) take one running-statistics step.
+  //   mode 2: backward of the batch norm whose input was q, applied to the gated gradient p.  A, B, C from tr_sums
+  //           (forward sums of q) and tr_bsums (sum p, sum p*q) as in BnBwdArgs with raw_sums; no act; tr_dgamma and
+  //           tr_dbeta are written.
+  int tr_mode, tr_p_f32;
+  const void* tr_p;
+  const bf16_t* tr_q;
+  bf16_t* tr_out;
+  const stat_t* tr_sums;
+  const stat_t* tr_bsums;
+  const float* tr_gamma;
+  const float* tr_beta;
+  float* tr_run_mean;
+  float* tr_run_var;
+  float* tr_dgamma;
+  float* tr_dbeta;
+  float tr_eps, tr_momentum;
+  int tr_rep_stride;     // stat_t elements between the copies of tr_sums and tr_bsums (0: one copy)
 };
+// whether the narrow kernel takes this layer with an input transform (a geometry conv_narrow_applies accepts, real input
+// channels, one tile per workgroup, LDS for the raw patches)
+bool conv_narrow_transforms(const GatherConvArgs& a, bool p_f32, bool with_q);
 hipError_t launch_conv_gather(const GatherConvArgs& a, hipStream_t s);
 // narrow layers (16 / 32 / 64 channels in and out, 3x3, unit stride): whole patch and whole filter on chip
 bool conv_narrow_applies(const GatherConvArgs& a);
@@ -144,6 +171,23 @@ struct ConvShape {
 // i.e. the batch-norm statistics of the tensor just produced
 hipError_t conv_forward(const ConvShape& c, const bf16_t* x, const bf16_t* w, const float* addend, float* out_f32,
                         bf16_t* out_b16, stat_t* stats, hipStream_t s, int stats_rep_stride = 0);
+// The same convolution of relu(batchnorm(x_raw)) with the batch-norm pass done on the patch in LDS (narrow layers, see
+// GatherConvArgs::tr_mode = 1): act_out receives relu(batchnorm(x_raw)) in bf16 as a pass of its own would have written
+// it; run_mean / run_var (optional) take one running-statistics step.  conv_forward_bn_applies says where.
+struct ConvInputBn {
+  const bf16_t* x_raw;   // [N, Hi, Wi, Cip] the batch norm's input
+  const stat_t* sums;    // its sums array (sum, sum of squares), complete
+  const float* gamma;
+  const float* beta;
+  bf16_t* act_out;       // [N, Hi, Wi, Cip]
+  float* run_mean;
+  float* run_var;
+  float eps, momentum;
+  int rep_stride;        // stat_t elements between the copies of sums (0: one copy)
+};
+bool conv_forward_bn_applies(const ConvShape& c);
+hipError_t conv_forward_bn(const ConvShape& c, const ConvInputBn& bn, const bf16_t* w, const float* addend, float* out_f32,
+                           bf16_t* out_b16, stat_t* stats, hipStream_t s, int stats_rep_stride = 0);
 // dx[N,Hi,Wi,Cip] = conv^T(dy[N,Ho,Wo,Co], wt[Cip][T][Co]) (+ addend, optionally only where addmask > 0)
 hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                       const bf16_t* addmask, float* out_f32, bf16_t* out_b16, hipStream_t s);

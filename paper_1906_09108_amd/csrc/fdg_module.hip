@@ -574,6 +574,23 @@ hipError_t mconv_forward(const fdg_module* m, const ConvInfo& c, const bf16_t* x
   ps.label(c.sh);
   return e;
 }
+// relu(batchnorm_b(x_raw)) -> act_out and the convolution of it, in one launch where the narrow kernel takes the batch-norm
+// pass on its patch (conv_forward_bn_applies); false: the caller runs the two launches
+bool forward_bn_fuses(const ConvInfo& c, const BnInfo& b) {
+  return b.C == c.sh.Cip && (long long)b.M == (long long)c.sh.N * c.sh.Hi * c.sh.Wi && conv_forward_bn_applies(c.sh);
+}
+hipError_t mconv_forward_after_bn(const fdg_module* m, const SlotView& v, const ConvInfo& c, const BnInfo& b, const bf16_t* x_raw,
+                                  bf16_t* act_out, const bf16_t* w, bf16_t* out_b16, stat_t* stats, bool replayed, hipStream_t s) {
+  ConvInputBn bn{};
+  bn.x_raw = x_raw; bn.sums = v.sums(b); bn.gamma = v.snap(b.gamma_off); bn.beta = v.snap(b.beta_off); bn.act_out = act_out;
+  if (!replayed) { bn.run_mean = m->running() + b.stat_off; bn.run_var = m->running() + b.stat_off + b.C; }
+  bn.eps = m->p.d.bn_eps; bn.momentum = m->p.d.bn_momentum; bn.rep_stride = m->p.stat_rep;
+  const double bytes = 2 * conv_in_elems(c.sh) * 2 + 2 * conv_w_elems(c.sh) + conv_out_elems(c.sh) * (out_b16 ? 2 : 0);
+  ProfScope ps(m, PC_CONV_FWD, conv_flops(c.sh), bytes, s);
+  const hipError_t e = conv_forward_bn(c.sh, bn, w, nullptr, nullptr, out_b16, stats, s, m->p.stat_rep);
+  ps.label(c.sh);
+  return e;
+}
 // ---- the side stream of the weight gradients (see SideStream) ----
 bool side_create(SideStream& sd) {
   bool ok = hipStreamCreateWithFlags(&sd.stream, hipStreamNonBlocking) == hipSuccess;
@@ -798,8 +815,12 @@ fdg_status forward_pass(fdg_module* m, const SlotView& v, const float* x_dev, fl
       const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]];
       bf16_t *t_c1 = v.act(L.act[0]), *t_a1 = v.act(L.act[1]), *t_c2 = v.act(L.act[2]);
       FDG_TRY(mconv_forward(m, c1, cur_b, v.W(c1), nullptr, nullptr, t_c1, v.sums(b1), s));
-      FDG_TRY(bn_apply(m, v, b1, t_c1, nullptr, nullptr, nullptr, nullptr, t_a1, replayed, s));
-      FDG_TRY(mconv_forward(m, c2, t_a1, v.W(c2), nullptr, nullptr, t_c2, v.sums(b2), s));
+      if (forward_bn_fuses(c2, b1)) {   // BN1 + ReLU on the patch of the second convolution
+        FDG_TRY(mconv_forward_after_bn(m, v, c2, b1, t_c1, t_a1, v.W(c2), t_c2, v.sums(b2), replayed, s));
+      } else {
+        FDG_TRY(bn_apply(m, v, b1, t_c1, nullptr, nullptr, nullptr, nullptr, t_a1, replayed, s));
+        FDG_TRY(mconv_forward(m, c2, t_a1, v.W(c2), nullptr, nullptr, t_c2, v.sums(b2), s));
+      }
       if (L.projects) {
         const ConvInfo& cp = p.convs[L.conv[2]];
         const BnInfo& bp = p.bns[L.bn[2]];

@@ -402,6 +402,80 @@ def test_conv_wgrad(case):
         assert rel(got, ref) <= F32_TOL
 
 
+FWD_BN_CASES = [  # (n, h, w, c): narrow layers, unit stride
+    (3, 7, 5, 16),        # ragged tile, odd image
+    (16, 32, 32, 16),     # several tiles per image
+    (128, 32, 32, 16),    # the ResNet-110 stage at the bench batch: 512 tiles of 256 pixels
+    (8, 16, 16, 32),
+    (128, 16, 16, 32),
+    (5, 8, 8, 64),
+    (128, 8, 8, 64),
+]
+
+
+@pytest.mark.parametrize("case", FWD_BN_CASES)
+def test_convolution_with_batch_norm_on_its_patch(case):
+    """fdgk_conv_fwd_bn: act = relu(batchnorm(x_raw)) written in bf16 and y = conv(act, w).  Reference: the oracle's batch norm
+    (fp32 definition) on x_raw, ReLU, then the oracle's convolution of the bf16 values the kernel wrote; and the fused launch
+    against the two launches it replaces (fdgk_bn_apply, then fdgk_conv_fwd), which must agree to a bf16 step of act."""
+    from paper_1906_09108_amd import kernels as K
+    t = _torch()
+    n, h, w, c = case
+    print("conv_fwd_bn", case, flush=True)
+    assert K.fdgk_conv_fwd_bn_applies(n, h, w, c, c)
+    r = np.random.default_rng(31 + n + c)
+    eps, mom = 1e-5, 0.1
+    m = n * h * w
+    x = bf16_round(r.standard_normal((n, c, h, w)) * (0.5 + r.random((1, c, 1, 1))) + r.standard_normal((1, c, 1, 1)))
+    wt = bf16_round(r.standard_normal((c, c, 3, 3)) * np.sqrt(2.0 / (c * 9)))
+    gamma = (1 + 0.2 * r.standard_normal(c)).astype(np.float32)
+    beta = (0.2 * r.standard_normal(c)).astype(np.float32)
+    y_bn, mean, var, invstd = K32.bn_fwd(x, gamma, beta, eps)
+    act_ref = np.maximum(y_bn.astype(np.float64), 0)
+    xd = to_dev_nhwc_b16(x)
+    sums = K.new_sums(c)
+    K.fdgk_bn_stats(xd.reshape(m, c), sums, m, c)
+    wd = t.from_numpy(wt.transpose(0, 2, 3, 1).copy()).to(t.bfloat16).contiguous().cuda()
+    gd, bd = t.from_numpy(gamma).cuda(), t.from_numpy(beta).cuda()
+    rm0, rv0 = r.standard_normal(c).astype(np.float32), (1 + r.random(c)).astype(np.float32)
+    rm, rv = t.from_numpy(rm0.copy()).cuda(), t.from_numpy(rv0.copy()).cuda()
+    act = t.full((n, h, w, c), float("nan"), dtype=t.bfloat16, device="cuda")
+    y16 = t.full((n, h, w, c), float("nan"), dtype=t.bfloat16, device="cuda")
+    st = K.new_sums(c)
+    K.fdgk_conv_fwd_bn(xd, sums, gd, bd, eps, act, rm, rv, mom, wd, y16, st, n, h, w, c, c)
+    t.cuda.synchronize()
+    act_got = nhwc_to_nchw(act)
+    assert rel(act_got, act_ref) <= B16_TOL
+    assert np.all(act_got >= 0)
+    # the convolution of exactly the values written
+    y_ref = K32.conv_fwd(act_got.astype(np.float32), wt, 1, 1).astype(np.float64)
+    y_got = nhwc_to_nchw(y16)
+    assert rel(y_got, y_ref) <= B16_TOL
+    yb = y16.to(t.float64).reshape(-1, c).cpu().numpy()
+    got = K.fdgk_sums_read(st, c)
+    assert rel(got[:c], yb.sum(0)) <= 1e-5
+    assert rel(got[c:], (yb * yb).sum(0)) <= 1e-5
+    # running statistics: one step with the unbiased variance
+    unbias = m / (m - 1.0)
+    assert rel(rm.cpu().numpy(), (1 - mom) * rm0 + mom * mean.astype(np.float64)) <= 1e-5
+    assert rel(rv.cpu().numpy(), (1 - mom) * rv0 + mom * var.astype(np.float64) * unbias) <= 1e-4
+    # the two launches it replaces
+    act2 = t.empty((m, c), dtype=t.bfloat16, device="cuda")
+    y2 = t.empty((n, h, w, c), dtype=t.bfloat16, device="cuda")
+    K.fdgk_bn_apply(xd.reshape(m, c), sums, gd, bd, None, None, act2, m, c, eps, 1)
+    K.fdgk_conv_fwd(act2, wd, None, None, y2, None, n, h, w, c, c, 3, 1)
+    t.cuda.synchronize()
+    assert rel(act.to(t.float32).reshape(m, c).cpu().numpy(), act2.to(t.float32).cpu().numpy().astype(np.float64)) <= 2.0 ** -8
+    assert rel(nhwc_to_nchw(y16), nhwc_to_nchw(y2)) <= B16_TOL
+
+
+def test_conv_fwd_bn_refuses_what_it_does_not_cover():
+    from paper_1906_09108_amd import kernels as K
+    assert not K.fdgk_conv_fwd_bn_applies(2, 8, 8, 128, 128)      # wide layer
+    assert not K.fdgk_conv_fwd_bn_applies(2, 8, 8, 16, 32)        # channels change
+    assert not K.fdgk_conv_fwd_bn_applies(128, 64, 64, 64, 64)    # more tiles than a workgroup each may take
+
+
 BN_CASES = [(189, 16), (4096, 16), (1000, 40), (512, 640), (16384, 32), (77, 2048)]
 
 
