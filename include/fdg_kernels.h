@@ -68,6 +68,20 @@ int fdgk_conv_dgrad(const void* dy_b16, const void* wt_b16, const float* addend_
                     float* dx_f32, void* dx_b16, int n, int h, int w, int ci, int co, int ksize, int stride,
                     void* hip_stream);
 
+/* The data gradient of a 3x3 unit-stride convolution whose incoming gradient dy is the apply half of a batch-norm
+ * backward (Eq. 8 / Eq. 9 through BN o conv), done on the convolution's input patch on chip:
+ *   dy = gamma * invstd * (g - sum g / M - xhat * sum(g xhat) / M),   dx = data gradient of dy (+ addend as fdgk_conv_dgrad),
+ * with g [n,h,w,co] the gated gradient at the batch norm's output (bf16, or fp32 with g_is_f32), x_b16 [n,h,w,co] the batch
+ * norm's input, x_sums its forward sums and gsums = (sum g, sum g*x) as fdgk_conv_dgrad_gated / _feeding_next leave them.
+ * dy_b16 [n,h,w,co] receives dy (what the weight gradient of the same convolution reads); dgamma = sum g xhat, dbeta = sum g.
+ * Narrow layers only (ci = co in {16, 32, 64}, at most 1024 pixel tiles): fdgk_conv_dgrad_bn_applies says (1 / 0); elsewhere
+ * the call returns 1 (hipErrorInvalidValue) and enqueues nothing.                                                        */
+int fdgk_conv_dgrad_bn_applies(int n, int h, int w, int ci, int co, int g_is_f32);
+int fdgk_conv_dgrad_bn(const void* g, int g_is_f32, const void* x_b16, const void* x_sums, const void* gsums, const float* gamma,
+                       float eps, void* dy_b16, float* dgamma, float* dbeta, const void* wt_b16, const float* addend_f32,
+                       const void* addmask_b16, float* dx_f32, void* dx_b16, int n, int h, int w, int ci, int co,
+                       void* hip_stream);
+
 /* The data gradient ending in the ReLU and the batch norm it back-propagates into next (Eq. 8 / Eq. 9 applied to
  * conv o ReLU o BN): with gate_b16 = the ReLU's output and bnx_b16 = the batch norm's input, both [n,h,w,cip],
  *   dx = gate > 0 ? (data gradient + addend) : 0,

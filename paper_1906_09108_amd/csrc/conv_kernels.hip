@@ -435,7 +435,7 @@ hipError_t conv_forward_bn(const ConvShape& c, const ConvInputBn& bn, const bf16
 static hipError_t conv_dgrad_impl(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                                   const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, stat_t* gsums, float* out_f32,
                                   bf16_t* out_b16, hipStream_t s, bool stats_f32 = false, int rep_stride = 0,
-                                  const bf16_t* dy2 = nullptr, const bf16_t* wt2 = nullptr);
+                                  const bf16_t* dy2 = nullptr, const bf16_t* wt2 = nullptr, const ConvInputBnBwd* bn = nullptr);
 
 hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                       const bf16_t* addmask, float* out_f32, bf16_t* out_b16, hipStream_t s) {
@@ -480,6 +480,27 @@ hipError_t conv_dgrad_gated(const ConvShape& c, const bf16_t* dy, const bf16_t* 
   return conv_dgrad_impl(c, dy, wt, addend, nullptr, gate, bnx, gsums, out_f32, out_b16, s, false, gsums_rep_stride);
 }
 
+bool conv_dgrad_bn_applies(const ConvShape& c, bool g_is_f32) {
+  if (c.stride != 1 || c.T != 9 || c.Ci != c.Cip) return false;
+  GatherConvArgs a{};
+  a.N = c.N; a.Hi = c.Ho(); a.Wi = c.Wo(); a.Ci = c.Co; a.Co = c.Cip; a.w_rows = c.Cip; a.Kw = c.T * c.Co;
+  a.OH = c.Hi; a.OW = c.Wi; a.OHf = c.Hi; a.OWf = c.Wi; a.in_stride = 1; a.out_stride = 1; a.ntaps = 9;
+  for (int r = 0; r < 3; ++r)
+    for (int q = 0; q < 3; ++q) a.tap[r * 3 + q] = pack_tap(1 - r, 1 - q, r * 3 + q);
+  return conv_narrow_transforms(a, g_is_f32, true);
+}
+
+hipError_t conv_dgrad_after_bn(const ConvShape& c, const ConvInputBnBwd& bn, const bf16_t* wt, const float* addend,
+                               const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, stat_t* gsums, bool sums_of_f32,
+                               float* out_f32, bf16_t* out_b16, hipStream_t s, int gsums_rep_stride) {
+  if (!conv_dgrad_bn_applies(c, bn.g_is_f32 != 0) || (!out_f32 && !out_b16)) return hipErrorInvalidValue;
+  const bool sums = gate || bnx || gsums;
+  if (sums && (!gate || !bnx || !gsums)) return hipErrorInvalidValue;
+  if (sums_of_f32 && (!sums || !out_f32)) return hipErrorInvalidValue;
+  return conv_dgrad_impl(c, nullptr, wt, addend, addmask, gate, bnx, gsums, out_f32, out_b16, s, sums_of_f32, gsums_rep_stride, nullptr,
+                         nullptr, &bn);
+}
+
 // the stride-2 wide path below takes both data gradients: 3x3 and 1x1 with the same stride-2 geometry and channel counts
 bool conv_dgrad_pair_applies(const ConvShape& c, const ConvShape& cp) {
   if (c.stride != 2 || cp.stride != 2 || c.T != 9 || cp.T != 1 || c.N != cp.N || c.Hi != cp.Hi || c.Wi != cp.Wi ||
@@ -500,7 +521,7 @@ hipError_t conv_dgrad_gated_pair(const ConvShape& c, const bf16_t* dy, const bf1
 static hipError_t conv_dgrad_impl(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                                   const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, stat_t* gsums, float* out_f32,
                                   bf16_t* out_b16, hipStream_t s, bool stats_f32, int rep_stride, const bf16_t* dy2,
-                                  const bf16_t* wt2) {
+                                  const bf16_t* wt2, const ConvInputBnBwd* bn) {
   GatherConvArgs a{};
   a.stats_rep_stride = rep_stride;
   a.in = dy; a.w = wt; a.addend = addend; a.addmask = addmask; a.out_f32 = out_f32; a.out_b16 = out_b16;
@@ -520,8 +541,19 @@ static hipError_t conv_dgrad_impl(const ConvShape& c, const bf16_t* dy, const bf
     } else {
       a.tap[0] = pack_tap(0, 0, 0);
     }
+    if (bn) {   // the batch-norm backward that produces dy, on the patch (narrow kernel)
+      if (!bn->g || !bn->x || !bn->sums || !bn->bsums || !bn->gamma || !bn->dgamma || !bn->dbeta || !bn->dy_out ||
+          !conv_narrow_transforms(a, bn->g_is_f32 != 0, true))
+        return hipErrorInvalidValue;
+      a.in = nullptr;
+      a.tr_mode = 2; a.tr_p = bn->g; a.tr_p_f32 = bn->g_is_f32 ? 1 : 0; a.tr_q = bn->x; a.tr_out = bn->dy_out;
+      a.tr_sums = bn->sums; a.tr_bsums = bn->bsums; a.tr_gamma = bn->gamma; a.tr_dgamma = bn->dgamma; a.tr_dbeta = bn->dbeta;
+      a.tr_eps = bn->eps; a.tr_rep_stride = bn->rep_stride;
+      return launch_conv_narrow(a, s);
+    }
     return launch_conv_gather(a, s);
   }
+  if (bn) return hipErrorInvalidValue;
   // stride 2: input pixels of one parity class (ph, pw) share one set of taps:
   // hi = 2*oh + ph receives tap r only if hi + 1 - r is even, from output row (hi + 1 - r) / 2.
   {

@@ -188,6 +188,31 @@ struct ConvInputBn {
 bool conv_forward_bn_applies(const ConvShape& c);
 hipError_t conv_forward_bn(const ConvShape& c, const ConvInputBn& bn, const bf16_t* w, const float* addend, float* out_f32,
                            bf16_t* out_b16, stat_t* stats, hipStream_t s, int stats_rep_stride = 0);
+// A data gradient whose input dy is the apply half of a batch-norm backward, done on the patch in LDS (narrow layers,
+// see GatherConvArgs::tr_mode = 2): dy = gamma*invstd*(g - sum g / M - xhat * sum(g xhat) / M) for the gated gradient g at
+// the batch norm's output and its input x, with the sums of g and g*x already in bsums (as a gated data gradient leaves
+// them).  dy_out receives dy in bf16 (what the weight gradient of the same convolution reads), dgamma / dbeta are
+// written.  Passed to the conv_dgrad_* calls below in place of their dy argument.
+struct ConvInputBnBwd {
+  const void* g;         // [N, Ho, Wo, Co] gated gradient, bf16 or fp32 (g_is_f32)
+  int g_is_f32;
+  const bf16_t* x;       // [N, Ho, Wo, Co] the batch norm's input
+  const stat_t* sums;    // forward sums of x
+  const stat_t* bsums;   // sum g, sum g*x
+  const float* gamma;
+  float* dgamma;
+  float* dbeta;
+  bf16_t* dy_out;        // [N, Ho, Wo, Co]
+  float eps;
+  int rep_stride;        // stat_t elements between the copies of sums and of bsums (0: one copy)
+};
+// whether the data gradient of c takes such an input (unit stride 3x3 narrow layer, one tile per workgroup)
+bool conv_dgrad_bn_applies(const ConvShape& c, bool g_is_f32);
+// conv_dgrad (gate, bnx, gsums all nullptr), conv_dgrad_gated (sums of the bf16 values) or conv_dgrad_feeding_next
+// (sums_of_f32: of the fp32 values, out_f32 required) with that input
+hipError_t conv_dgrad_after_bn(const ConvShape& c, const ConvInputBnBwd& bn, const bf16_t* wt, const float* addend,
+                               const bf16_t* addmask, const bf16_t* gate, const bf16_t* bnx, stat_t* gsums, bool sums_of_f32,
+                               float* out_f32, bf16_t* out_b16, hipStream_t s, int gsums_rep_stride = 0);
 // dx[N,Hi,Wi,Cip] = conv^T(dy[N,Ho,Wo,Co], wt[Cip][T][Co]) (+ addend, optionally only where addmask > 0)
 hipError_t conv_dgrad(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const float* addend,
                       const bf16_t* addmask, float* out_f32, bf16_t* out_b16, hipStream_t s);

@@ -79,7 +79,7 @@ struct Plan {
   // intermediates: inside every slot, or (replay) once per module at o_inter
   size_t s_sums = 0, s_xin = 0, s_acts = 0, s_pooled = 0, s_dl = 0, s_logits = 0;
   size_t o_inter = 0, inter_bytes = 0;
-  size_t o_S[2] = {0, 0}, o_G[2] = {0, 0}, o_GB[2] = {0, 0}, o_T[2] = {0, 0}, o_TP = 0, o_TPB = 0, o_dp = 0;
+  size_t o_S[2] = {0, 0}, o_G[2] = {0, 0}, o_GB[2] = {0, 0}, o_T[3] = {0, 0, 0}, o_TP = 0, o_TPB = 0, o_dp = 0;
   size_t o_wscratch = 0, wscratch_bytes = 0;   // partial sums of the split weight gradient
   size_t o_dwscratch = 0, dwscratch_bytes = 0; // the same for depthwise convolutions (they run on the caller's stream)
   size_t o_col = 0, o_colb = 0, col_bytes = 0; // operand rows of a 7x7 stem (launch_im2col7): the forward's and the backward's copy
@@ -370,7 +370,7 @@ bool build_plan(const fdg_module_desc* desc, int save_mode, Plan& p, fdg_status*
   for (int i = 0; i < 2; ++i) p.o_S[i] = take(p.maxE * 4);
   for (int i = 0; i < 2; ++i) p.o_G[i] = take(p.maxE * 4);
   for (int i = 0; i < 2; ++i) p.o_GB[i] = take(p.maxE * 2);
-  for (int i = 0; i < 2; ++i) p.o_T[i] = take(p.maxE * 2);
+  for (int i = 0; i < 3; ++i) p.o_T[i] = take(p.maxE * 2);
   p.o_TP = take(std::max(p.maxE, p.is_top ? (size_t)1 + (size_t)N * desc->num_classes : (size_t)0) * 4);
   // the backward's own copy: a forward and a delayed backward of different contexts share no temporary, so they may
   // run on two streams at once (delay >= 1, stored form)
@@ -754,19 +754,37 @@ hipError_t bn_backward_fed_from_above(const fdg_module* m, const SlotView& v, co
 // Data gradient of convolution c into g (bf16), then the backward of the ReLU (gate = its output) and of the batch
 // norm b (input x) that precede the convolution.  Where the wide kernels run, the gate and the two sums of the
 // batch-norm backward are taken in the data gradient's output stage and one pass over g is saved.
+// first half of the function below where the data gradient's output stage gates and sums: g = gate > 0 ? dgrad + addend : 0
+// (bf16) and the two sums of batch norm b's backward in the module's bsums
+bool dgrad_gates_for(const ConvInfo& c, const BnInfo& b) { return conv_dgrad_gates(c.sh) && b.C == c.sh.Cip; }
+hipError_t gated_dgrad(const fdg_module* m, const ConvInfo& c, const bf16_t* dy, const bf16_t* wt, const float* dgrad_addend,
+                       const BnInfo& b, const bf16_t* gate, const bf16_t* x, bf16_t* g, hipStream_t s) {
+  if (hipError_t e = side_wait_readers(m, g, s); e != hipSuccess) return e;
+  const double bytes = 2 * conv_out_elems(c.sh) + 2 * conv_w_elems(c.sh) + conv_in_elems(c.sh) * ((dgrad_addend ? 4 : 0) + 2 + 2 + 2);
+  ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c.sh), bytes, s);
+  const hipError_t e = conv_dgrad_gated(c.sh, dy, wt, dgrad_addend, gate, x, m->bsums(b), nullptr, g, s, m->p.stat_rep);
+  ps.label(c.sh);
+  return e;
+}
+// The batch-norm backward of b (input x, gated gradient g with its two sums in bsums) as the input transform of the data
+// gradient that consumes it (conv_dgrad_after_bn): where the narrow kernel takes it, dy never makes a pass of its own
+ConvInputBnBwd bn_bwd_input(const fdg_module* m, const SlotView& v, const BnInfo& b, const void* g, bool g_f32, const bf16_t* x,
+                            bf16_t* dy_out) {
+  ConvInputBnBwd bn{};
+  bn.g = g; bn.g_is_f32 = g_f32 ? 1 : 0; bn.x = x; bn.sums = v.sums(b); bn.bsums = m->bsums(b); bn.gamma = v.snap(b.gamma_off);
+  bn.dgamma = m->grads() + b.gamma_off; bn.dbeta = m->grads() + b.beta_off; bn.dy_out = dy_out;
+  bn.eps = m->p.d.bn_eps; bn.rep_stride = m->p.stat_rep;
+  return bn;
+}
+bool bwd_bn_fuses(const ConvInfo& c, const BnInfo& b, bool g_f32) {
+  return b.C == c.sh.Co && (long long)b.M == (long long)c.sh.N * c.sh.Ho() * c.sh.Wo() && conv_dgrad_bn_applies(c.sh, g_f32);
+}
+
 hipError_t dgrad_relu_bn_backward(const fdg_module* m, const SlotView& v, const ConvInfo& c, const bf16_t* dy, const bf16_t* wt,
                                   const float* dgrad_addend, const BnInfo& b, const bf16_t* gate, const bf16_t* x, bf16_t* g,
                                   const float* bn_addend, float* out_f32, bf16_t* out_b16, hipStream_t s) {
-  if (conv_dgrad_gates(c.sh) && b.C == c.sh.Cip) {
-    if (hipError_t e = side_wait_readers(m, g, s); e != hipSuccess) return e;
-    {
-      const double bytes = 2 * conv_out_elems(c.sh) + 2 * conv_w_elems(c.sh) + conv_in_elems(c.sh) * ((dgrad_addend ? 4 : 0) + 2 + 2 + 2);
-      ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c.sh), bytes, s);
-      const hipError_t e = conv_dgrad_gated(c.sh, dy, wt, dgrad_addend, gate, x, m->bsums(b), nullptr, g, s,
-                                            m->p.stat_rep);
-      ps.label(c.sh);
-      if (e != hipSuccess) return e;
-    }
+  if (dgrad_gates_for(c, b)) {
+    if (hipError_t e = gated_dgrad(m, c, dy, wt, dgrad_addend, b, gate, x, g, s); e != hipSuccess) return e;
     return bn_backward_after_gated_dgrad(m, v, b, g, x, bn_addend, out_f32, out_b16, s);
   }
   hipError_t e = mconv_dgrad(m, c, dy, wt, dgrad_addend, nullptr, nullptr, g, s);
@@ -1088,12 +1106,40 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
       const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]];
       const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]];
       const bf16_t *t_c1 = v.act(L.act[0]), *t_a1 = v.act(L.act[1]), *t_c2 = v.act(L.act[2]), *t_y = v.act(L.out_b);
-      // final ReLU mask (y > 0) then BN2
-      if (fed_here) FDG_TRY(bn_backward_fed_from_above(m, v, b2, m->G(cur), t_c2, m->T(0), s));
-      else FDG_TRY(bn_backward(m, v, b2, m->G(cur), true, t_y, t_c2, nullptr, nullptr, m->T(0), s));
-      FDG_TRY(mconv_wgrad(m, c2, t_a1, m->T(0), s));
-      FDG_TRY(dgrad_relu_bn_backward(m, v, c2, m->T(0), v.Wt(c2), nullptr, b1, t_a1, t_c1, m->T(1), nullptr, nullptr, m->T(0), s));
-      FDG_TRY(mconv_wgrad(m, c1, in_b, m->T(0), s));
+      // final ReLU mask (y > 0) then BN2; weight gradient and data gradient of conv2 (through ReLU and BN1); weight gradient
+      // and data gradient of conv1.  Where the narrow kernel runs, the apply half of each batch-norm backward is done on
+      // the patch of the data gradient that consumes it (fuse2: BN2 into conv2's, fuse1: BN1 into conv1's); that kernel
+      // also writes the batch norm's result, which the weight gradient of the same convolution reads afterwards.
+      const bool gated = dgrad_gates_for(c2, b1);
+      const bool fuse2 = fed_here && gated && bwd_bn_fuses(c2, b2, /*g_f32=*/true);
+      const bool fuse1 = gated && !L.projects && need_dx && bwd_bn_fuses(c1, b1, /*g_f32=*/false);
+      bf16_t* dy_c1 = m->T(0);
+      if (fuse2) {
+        FDG_TRY(side_wait_readers(m, m->T(0), s));
+        FDG_TRY(side_wait_readers(m, m->T(1), s));
+        {
+          const ConvInputBnBwd bn = bn_bwd_input(m, v, b2, m->G(cur), true, t_c2, m->T(0));
+          const double bytes = conv_out_elems(c2.sh) * (4 + 2 + 2) + 2 * conv_w_elems(c2.sh) + conv_in_elems(c2.sh) * (2 + 2 + 2);
+          ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c2.sh), bytes, s);
+          const hipError_t e = conv_dgrad_after_bn(c2.sh, bn, v.Wt(c2), nullptr, nullptr, t_a1, t_c1, m->bsums(b1), false, nullptr,
+                                                   m->T(1), s, p.stat_rep);
+          ps.label(c2.sh);
+          FDG_TRY(e);
+        }
+        FDG_TRY(mconv_wgrad(m, c2, t_a1, m->T(0), s));
+      } else {
+        if (fed_here) FDG_TRY(bn_backward_fed_from_above(m, v, b2, m->G(cur), t_c2, m->T(0), s));
+        else FDG_TRY(bn_backward(m, v, b2, m->G(cur), true, t_y, t_c2, nullptr, nullptr, m->T(0), s));
+        FDG_TRY(mconv_wgrad(m, c2, t_a1, m->T(0), s));
+        if (gated) FDG_TRY(gated_dgrad(m, c2, m->T(0), v.Wt(c2), nullptr, b1, t_a1, t_c1, m->T(1), s));
+        else FDG_TRY(dgrad_relu_bn_backward(m, v, c2, m->T(0), v.Wt(c2), nullptr, b1, t_a1, t_c1, m->T(1), nullptr, nullptr, m->T(0), s));
+      }
+      if (fuse1) {
+        dy_c1 = m->T(2);   // written by conv1's data gradient below; T(0) may still be read by conv2's weight gradient
+      } else {
+        if (gated) FDG_TRY(bn_backward_after_gated_dgrad(m, v, b1, m->T(1), t_c1, nullptr, nullptr, m->T(0), s));
+        FDG_TRY(mconv_wgrad(m, c1, in_b, dy_c1, s));
+      }
       if (L.projects) {
         const ConvInfo& cp = p.convs[L.conv[2]];
         const BnInfo& bp = p.bns[L.bn[2]];
@@ -1109,7 +1155,23 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
         // backward: the ReLU gate and the two sums of the batch norm.
         const bf16_t* bnx = nullptr;
         const BnInfo* bb = li > 0 ? closing_bn(p, v, p.L[li - 1], &bnx) : nullptr;
-        if (bb && bb->C == c1.sh.Cip && conv_dgrad_feeds_next(c1.sh)) {
+        const bool feeds = bb && bb->C == c1.sh.Cip && conv_dgrad_feeds_next(c1.sh);
+        if (fuse1) {
+          FDG_TRY(side_wait_readers(m, m->T(2), s));
+          FDG_TRY(side_wait_readers(m, m->GB(nxt), s));
+          {
+            const ConvInputBnBwd bn = bn_bwd_input(m, v, b1, m->T(1), false, t_c1, m->T(2));
+            const double bytes = conv_out_elems(c1.sh) * (2 + 2 + 2) + 2 * conv_w_elems(c1.sh) +
+                                 conv_in_elems(c1.sh) * (4 + 2 + (feeds ? 2 + 2 : 0) + 4 + 2);
+            ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c1.sh), bytes, s);
+            const hipError_t e = conv_dgrad_after_bn(c1.sh, bn, v.Wt(c1), m->G(cur), t_y, feeds ? in_b : nullptr, feeds ? bnx : nullptr,
+                                                     feeds ? m->bsums(*bb) : nullptr, feeds, m->G(nxt), m->GB(nxt), s, p.stat_rep);
+            ps.label(c1.sh);
+            FDG_TRY(e);
+          }
+          fed = feeds;
+          FDG_TRY(mconv_wgrad(m, c1, in_b, m->T(2), s));
+        } else if (feeds) {
           FDG_TRY(side_wait_readers(m, m->GB(nxt), s));
           const double bytes = 2 * conv_out_elems(c1.sh) + 2 * conv_w_elems(c1.sh) + conv_in_elems(c1.sh) * (4 + 2 + 2 + 2 + 4 + 2);
           ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c1.sh), bytes, s);

@@ -77,6 +77,27 @@ int fdgk_conv_fwd_bn(const void* x_raw_b16, const void* x_sums, const float* gam
                               static_cast<stat_t*>(stats_sums), st(hip_stream));
 }
 
+int fdgk_conv_dgrad_bn_applies(int n, int h, int w, int ci, int co, int g_is_f32) {
+  ConvShape c;
+  return conv_shape(c, n, h, w, ci, co, 3, 1) && conv_dgrad_bn_applies(c, g_is_f32 != 0) ? 1 : 0;
+}
+
+int fdgk_conv_dgrad_bn(const void* g, int g_is_f32, const void* x_b16, const void* x_sums, const void* gsums, const float* gamma,
+                       float eps, void* dy_b16, float* dgamma, float* dbeta, const void* wt_b16, const float* addend_f32,
+                       const void* addmask_b16, float* dx_f32, void* dx_b16, int n, int h, int w, int ci, int co,
+                       void* hip_stream) {
+  ConvShape c;
+  if (!g || !x_b16 || !x_sums || !gsums || !gamma || !dy_b16 || !dgamma || !dbeta || !wt_b16 || (!dx_f32 && !dx_b16) ||
+      !conv_shape(c, n, h, w, ci, co, 3, 1))
+    return (int)hipErrorInvalidValue;
+  ConvInputBnBwd bn{};
+  bn.g = g; bn.g_is_f32 = g_is_f32 ? 1 : 0; bn.x = static_cast<const bf16_t*>(x_b16); bn.sums = static_cast<const stat_t*>(x_sums);
+  bn.bsums = static_cast<const stat_t*>(gsums); bn.gamma = gamma; bn.dgamma = dgamma; bn.dbeta = dbeta;
+  bn.dy_out = static_cast<bf16_t*>(dy_b16); bn.eps = eps;
+  return (int)conv_dgrad_after_bn(c, bn, static_cast<const bf16_t*>(wt_b16), addend_f32, static_cast<const bf16_t*>(addmask_b16),
+                                  nullptr, nullptr, nullptr, false, dx_f32, static_cast<bf16_t*>(dx_b16), st(hip_stream));
+}
+
 int fdgk_conv_dgrad(const void* dy_b16, const void* wt_b16, const float* addend_f32, const void* addmask_b16,
                     float* dx_f32, void* dx_b16, int n, int h, int w, int ci, int co, int ksize, int stride,
                     void* hip_stream) {

@@ -6,7 +6,7 @@ import ctypes
 
 from .binding import _ptr, _stream_handle, load
 
-KERNEL_EXPORTS = ["fdgk_conv_fwd", "fdgk_conv_fwd_bn_applies", "fdgk_conv_fwd_bn", "fdgk_conv_dgrad", "fdgk_conv_dgrad_gated", "fdgk_conv_dgrad_feeding_next", "fdgk_conv_dgrad_gates", "fdgk_conv_dgrad_pair_applies", "fdgk_conv_dgrad_gated_pair", "fdgk_bn_bwd_gated", "fdgk_conv_wgrad", "fdgk_conv_wgrad_scratch_bytes", "fdgk_bn_stats", "fdgk_bn_apply",
+KERNEL_EXPORTS = ["fdgk_conv_fwd", "fdgk_conv_fwd_bn_applies", "fdgk_conv_fwd_bn", "fdgk_conv_dgrad_bn_applies", "fdgk_conv_dgrad_bn", "fdgk_conv_dgrad", "fdgk_conv_dgrad_gated", "fdgk_conv_dgrad_feeding_next", "fdgk_conv_dgrad_gates", "fdgk_conv_dgrad_pair_applies", "fdgk_conv_dgrad_gated_pair", "fdgk_bn_bwd_gated", "fdgk_conv_wgrad", "fdgk_conv_wgrad_scratch_bytes", "fdgk_bn_stats", "fdgk_bn_apply",
                   "fdgk_bn_bwd", "fdgk_sgd", "fdgk_bn_bwd_static", "fdgk_bn_bwd_static_max_c", "fdgk_sums_bytes", "fdgk_sums_read",
                   "fdgk_avgpool", "fdgk_fc_fwd", "fdgk_softmax_ce", "fdgk_fc_bwd", "fdgk_pool_bwd", "fdgk_nchw_to_nhwc", "fdgk_nhwc_to_nchw",
                   "fdgk_im2col7", "fdgk_maxpool3s2", "fdgk_maxpool3s2_bwd", "fdgk_dwconv3_fwd", "fdgk_dwconv3_dgrad",
@@ -22,6 +22,8 @@ def _lib():
         lib.fdgk_conv_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
         lib.fdgk_conv_dgrad.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
         lib.fdgk_conv_fwd_bn_applies.argtypes = [i, i, i, i, i]
+        lib.fdgk_conv_dgrad_bn_applies.argtypes = [i, i, i, i, i, i]
+        lib.fdgk_conv_dgrad_bn.argtypes = [vp, i, vp, vp, vp, vp, f, vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, vp]
         lib.fdgk_conv_fwd_bn.argtypes = [vp, vp, vp, vp, f, vp, vp, vp, f, vp, vp, vp, i, i, i, i, i, vp]
         lib.fdgk_conv_dgrad_gated.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
         lib.fdgk_conv_dgrad_feeding_next.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
@@ -101,6 +103,17 @@ def fdgk_conv_fwd_bn(x_raw_b16, x_sums, gamma, beta, eps, act_b16, run_mean, run
     _ok(_lib().fdgk_conv_fwd_bn(_ptr(x_raw_b16), _ptr(x_sums), _ptr(gamma), _ptr(beta), eps, _ptr(act_b16), _ptr(run_mean),
                                 _ptr(run_var), momentum, _ptr(w_b16), _ptr(y_b16), _ptr(stats_sums), n, h, w, ci, co,
                                 _stream_handle(stream)), "fdgk_conv_fwd_bn")
+
+
+def fdgk_conv_dgrad_bn_applies(n, h, w, ci, co, g_is_f32) -> bool:
+    return bool(_lib().fdgk_conv_dgrad_bn_applies(n, h, w, ci, co, 1 if g_is_f32 else 0))
+
+
+def fdgk_conv_dgrad_bn(g, g_is_f32, x_b16, x_sums, gsums, gamma, eps, dy_b16, dgamma, dbeta, wt_b16, addend_f32, addmask_b16, dx_f32,
+                       dx_b16, n, h, w, ci, co, stream=None):
+    _ok(_lib().fdgk_conv_dgrad_bn(_ptr(g), 1 if g_is_f32 else 0, _ptr(x_b16), _ptr(x_sums), _ptr(gsums), _ptr(gamma), eps,
+                                  _ptr(dy_b16), _ptr(dgamma), _ptr(dbeta), _ptr(wt_b16), _ptr(addend_f32), _ptr(addmask_b16),
+                                  _ptr(dx_f32), _ptr(dx_b16), n, h, w, ci, co, _stream_handle(stream)), "fdgk_conv_dgrad_bn")
 
 
 def fdgk_conv_dgrad(dy_b16, wt_b16, addend_f32, addmask_b16, dx_f32, dx_b16, n, h, w, ci, co, ksize, stride, stream=None):

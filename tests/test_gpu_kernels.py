@@ -469,6 +469,71 @@ def test_convolution_with_batch_norm_on_its_patch(case):
     assert rel(nhwc_to_nchw(y16), nhwc_to_nchw(y2)) <= B16_TOL
 
 
+@pytest.mark.parametrize("g_f32", [False, True])
+@pytest.mark.parametrize("case", [(3, 7, 5, 16), (16, 32, 32, 16), (128, 16, 16, 32), (5, 8, 8, 64), (128, 8, 8, 64)])
+def test_data_gradient_with_batch_norm_backward_on_its_patch(case, g_f32):
+    """fdgk_conv_dgrad_bn on a gated gradient g with its sums, as the data gradient of the convolution ABOVE leaves them
+    (fdgk_conv_dgrad_gated: bf16 g, sums of the bf16 values; fdgk_conv_dgrad_feeding_next: fp32 g, sums of the fp32 values).
+    Reference: the oracle's batch-norm backward of that g, rounded to bf16 as the kernel writes it, then the oracle's data
+    gradient; and the two launches it replaces (fdgk_bn_bwd_gated, fdgk_conv_dgrad)."""
+    from paper_1906_09108_amd import kernels as K
+    t = _torch()
+    n, h, w, c = case
+    print("conv_dgrad_bn", case, g_f32, flush=True)
+    assert K.fdgk_conv_dgrad_bn_applies(n, h, w, c, c, g_f32)
+    m = n * h * w
+    eps = 1e-5
+    r = np.random.default_rng(41 + n + c)
+    full = (n, h, w, c, c, 3, 1)
+    _, w_up, dy_up, _, _ = _conv_data(full, 42)                      # the convolution above: its data gradient makes g
+    _, wt, _, _, _ = _conv_data(full, 43)                            # the convolution whose data gradient is under test
+    gate = bf16_round(np.maximum(r.standard_normal((n, c, h, w)), 0))
+    x = bf16_round(r.standard_normal((n, c, h, w)) * (0.5 + r.random((1, c, 1, 1))) + r.standard_normal((1, c, 1, 1)))
+    gamma = (1 + 0.2 * r.standard_normal(c)).astype(np.float32)
+    tr = lambda a: t.from_numpy(a.transpose(1, 2, 3, 0).copy()).to(t.bfloat16).contiguous().cuda()
+    gsums = K.new_sums(c)
+    g32 = t.zeros((n, h, w, c), dtype=t.float32, device="cuda")
+    g16 = t.zeros((n, h, w, c), dtype=t.bfloat16, device="cuda")
+    xd, gated = to_dev_nhwc_b16(x), to_dev_nhwc_b16(gate)
+    if g_f32:
+        K.fdgk_conv_dgrad_feeding_next(to_dev_nhwc_b16(dy_up), tr(w_up), None, None, gated, xd, gsums, g32, g16, n, h, w, c, c, 3, 1)
+    else:
+        K.fdgk_conv_dgrad_gated(to_dev_nhwc_b16(dy_up), tr(w_up), None, gated, xd, gsums, None, g16, n, h, w, c, c, 3, 1)
+    sums = K.new_sums(c)
+    K.fdgk_bn_stats(xd.reshape(m, c), sums, m, c)
+    gd = t.from_numpy(gamma).cuda()
+    add = r.standard_normal((n, c, h, w)).astype(np.float32)
+    mask = bf16_round(np.maximum(r.standard_normal((n, c, h, w)), 0))
+    dy16 = t.full((n, h, w, c), float("nan"), dtype=t.bfloat16, device="cuda")
+    dx32 = t.full((n, h, w, c), float("nan"), dtype=t.float32, device="cuda")
+    dx16 = t.zeros((n, h, w, c), dtype=t.bfloat16, device="cuda")
+    dg, db = t.empty(c, dtype=t.float32, device="cuda"), t.empty(c, dtype=t.float32, device="cuda")
+    K.fdgk_conv_dgrad_bn(g32 if g_f32 else g16, g_f32, xd, sums, gsums, gd, eps, dy16, dg, db, tr(wt), to_dev_nhwc_f32(add),
+                         to_dev_nhwc_b16(mask), dx32, dx16, n, h, w, c, c)
+    t.cuda.synchronize()
+    # oracle: batch-norm backward of the g the kernel read
+    g_host = nhwc_to_nchw(g32 if g_f32 else g16).astype(np.float32)
+    _, mean, var, invstd = K32.bn_fwd(x.astype(np.float32), gamma, np.zeros(c, np.float32), eps)
+    dy_ref, dgamma_ref, dbeta_ref = K32.bn_bwd(x.astype(np.float32), g_host, gamma, mean, invstd)
+    assert rel(db.cpu().numpy(), dbeta_ref.astype(np.float64)) <= F32_TOL
+    assert rel(dg.cpu().numpy(), dgamma_ref.astype(np.float64)) <= F32_TOL
+    dy_got = nhwc_to_nchw(dy16)
+    assert rel(dy_got, dy_ref.astype(np.float64)) <= B16_TOL
+    # the data gradient of exactly the values written, plus the masked addend
+    dx_ref = K32.conv_bwd_data(dy_got.astype(np.float32), wt, x.shape, 1, 1).astype(np.float64) + add * (mask > 0)
+    assert rel(nhwc_to_nchw(dx32), dx_ref) <= F32_TOL
+    assert rel(nhwc_to_nchw(dx16), dx_ref) <= B16_TOL
+    # the two launches it replaces
+    dy2 = t.empty((m, c), dtype=t.bfloat16, device="cuda")
+    dg2, db2 = t.empty(c, dtype=t.float32, device="cuda"), t.empty(c, dtype=t.float32, device="cuda")
+    if not g_f32:
+        K.fdgk_bn_bwd_gated(g16.reshape(m, c), xd.reshape(m, c), sums, gd, gsums, None, None, dy2, dg2, db2, m, c, eps)
+        t.cuda.synchronize()
+        assert rel(dy16.to(t.float32).reshape(m, c).cpu().numpy(), dy2.to(t.float32).cpu().numpy().astype(np.float64)) <= 2.0 ** -8
+        assert rel(dg.cpu().numpy(), dg2.cpu().numpy().astype(np.float64)) <= 1e-5
+        assert rel(db.cpu().numpy(), db2.cpu().numpy().astype(np.float64)) <= 1e-6
+
+
 def test_conv_fwd_bn_refuses_what_it_does_not_cover():
     from paper_1906_09108_amd import kernels as K
     assert not K.fdgk_conv_fwd_bn_applies(2, 8, 8, 128, 128)      # wide layer
