@@ -365,6 +365,29 @@ __global__ __launch_bounds__(256) void conv_narrow_tr_kernel(GatherConvArgs a, N
   unsigned char* rawq = rawp + (size_t)units * (PF32 ? 32 : 16);
   if (tid < 8) reinterpret_cast<uint4*>(patch + (size_t)units * 16)[tid] = make_uint4(0u, 0u, 0u, 0u);
 
+  // ---- the words of the sums, requested first and used last (below, after everything else has been issued and the
+  //      fragment addresses worked out), so that this trip to memory runs beside the others.  Eight lanes per channel,
+  //      one per copy of the sums; slot sl of a thread is (channel, copy) number tid + 256 sl ----
+  constexpr int NS = (8 * CI + 255) / 256, NSUM = WQ ? 4 : 2;
+  long long w_hi[NS][NSUM], w_lo[NS][NSUM];
+  double w_big[NS][NSUM];
+  float w_gamma[NS], w_beta[NS];
+#pragma unroll
+  for (int sl = 0; sl < NS; ++sl) {
+    const int t = tid + 256 * sl, c = t >> 3, rp = t & 7, rep = a.tr_rep_stride;
+    const bool has = t < 8 * CI && (rep > 0 || rp == 0);       // a single copy: only the first lane of the eight reads
+    const bool first = t < 8 * CI && rp == 0;
+    w_gamma[sl] = first ? a.tr_gamma[c] : 0.f;
+    w_beta[sl] = (first && !WQ) ? a.tr_beta[c] : 0.f;
+#pragma unroll
+    for (int k = 0; k < NSUM; ++k) {
+      const stat_t* q = (k < 2 ? a.tr_sums : a.tr_bsums) + (size_t)(k & 1) * CI + (has ? c : 0) + (size_t)(has && rep > 0 ? rp : 0) * rep;
+      w_hi[sl][k] = has ? q[0] : 0;
+      w_lo[sl][k] = has ? q[2 * (size_t)CI] : 0;
+      w_big[sl][k] = has ? __builtin_bit_cast(double, q[4 * (size_t)CI]) : 0.0;
+    }
+  }
+
   // ---- the raw patches: row r holds pixel m0 - W - 1 + r (rows that do not exist read some row that does) ----
   {
     const int units_p = units * (PF32 ? 2 : 1);
@@ -402,59 +425,6 @@ __global__ __launch_bounds__(256) void conv_narrow_tr_kernel(GatherConvArgs a, N
       }
   }
 
-  // ---- per-channel coefficients from the exact sums (the same expressions as the batch-norm kernels).  Eight lanes per
-  //      channel, one per copy of the sums: all words are requested at once (taken copy after copy by one thread they
-  //      are seven dependent trips to memory), the integer words are added across the lanes, lane 0 of the eight works
-  //      out the channel's constants ----
-  for (int t0 = 0; t0 < 8 * CI; t0 += 256) {
-    const int t = t0 + tid;                    // 8 * CI is a multiple of 64: whole waves take part in the shuffles
-    if (t0 + (tid & ~63) >= 8 * CI) break;
-    const int c = t >> 3, rp = t & 7, rep = a.tr_rep_stride;
-    const bool has = rep > 0 || rp == 0;       // a single copy: only the first lane reads
-    auto total = [&](const stat_t* stats, int which) {
-      const stat_t* q = stats + (size_t)which * CI + c + (size_t)(rep > 0 ? rp : 0) * rep;
-      long long hi = has ? q[0] : 0, lo = has ? q[2 * (size_t)CI] : 0;
-      double big = has ? __builtin_bit_cast(double, q[4 * (size_t)CI]) : 0.0;
-#pragma unroll
-      for (int off = 1; off < 8; off <<= 1) {
-        hi += __shfl_xor(hi, off);
-        lo += __shfl_xor(lo, off);
-        big += __shfl_xor(big, off);
-      }
-      return stat_value(hi, lo, __builtin_bit_cast(long long, big));
-    };
-    const double s1 = total(a.tr_sums, 0), s2 = total(a.tr_sums, 1);
-    double t1 = 0.0, t2 = 0.0;
-    if (WQ) { t1 = total(a.tr_bsums, 0); t2 = total(a.tr_bsums, 1); }
-    if (rp != 0) continue;
-    const double invMd = 1.0 / (double)Mtot;
-    const double md = s1 * invMd;
-    const double var = fmax(s2 * invMd - md * md, 0.0);
-    const float mean = (float)md, is = rsqrtf((float)var + a.tr_eps);
-    const float g = a.tr_gamma[c] * is;
-    float A = g, B = 0.f, C;
-    if (!WQ) {
-      C = a.tr_beta[c] - mean * g;
-      if (blockIdx.x == 0 && a.tr_run_mean) {
-        const float unbias = Mtot > 1 ? (float)Mtot / (float)(Mtot - 1) : 1.f, mom = a.tr_momentum;
-        a.tr_run_mean[c] = (1.f - mom) * a.tr_run_mean[c] + mom * mean;
-        a.tr_run_var[c] = (1.f - mom) * a.tr_run_var[c] + mom * (float)var * unbias;
-      }
-    } else {
-      const float invM = (float)invMd;
-      const float b1 = (float)t1;
-      const float b2 = is * (float)(t2 - md * t1);     // sum g*xhat from sum g*x and sum g, the difference in double
-      const float k1 = b1 * invM, k2 = b2 * invM;
-      B = -g * k2 * is;
-      C = -g * k1 + g * k2 * is * mean;
-      if (blockIdx.x == 0) {
-        a.tr_dbeta[c] = b1;
-        a.tr_dgamma[c] = b2;
-      }
-    }
-    coef[c] = A; coef[CI + c] = B; coef[2 * CI + c] = C;
-  }
-
   // ---- LDS address of this lane's pixel fragment for every pixel block and step (as conv_narrow_kernel) ----
   constexpr int SA = CI == 64 ? 9 : S;
   const unsigned zero_addr = (unsigned)units * 16u;
@@ -483,6 +453,56 @@ __global__ __launch_bounds__(256) void conv_narrow_tr_kernel(GatherConvArgs a, N
         xaddr[j][s] = addr;
       }
     }
+  }
+
+  // ---- per-channel coefficients from the exact sums (the same expressions as the batch-norm kernels): the integer
+  //      words are added across the eight lanes of a channel, lane 0 of the eight works out the channel's constants ----
+#pragma unroll
+  for (int sl = 0; sl < NS; ++sl) {
+    if (256 * sl + (tid & ~63) >= 8 * CI) break;               // whole waves take part in the shuffles (8 CI is a multiple of 64)
+    const int t = tid + 256 * sl, c = t >> 3, rp = t & 7;
+    double tot[NSUM];
+#pragma unroll
+    for (int k = 0; k < NSUM; ++k) {
+      long long hi = w_hi[sl][k], lo = w_lo[sl][k];
+      double big = w_big[sl][k];
+#pragma unroll
+      for (int off = 1; off < 8; off <<= 1) {
+        hi += __shfl_xor(hi, off);
+        lo += __shfl_xor(lo, off);
+        big += __shfl_xor(big, off);
+      }
+      tot[k] = stat_value(hi, lo, __builtin_bit_cast(long long, big));
+    }
+    if (rp != 0) continue;
+    const double s1 = tot[0], s2 = tot[1];
+    const double invMd = 1.0 / (double)Mtot;
+    const double md = s1 * invMd;
+    const double var = fmax(s2 * invMd - md * md, 0.0);
+    const float mean = (float)md, is = rsqrtf((float)var + a.tr_eps);
+    const float g = w_gamma[sl] * is;
+    float A = g, B = 0.f, C;
+    if (!WQ) {
+      C = w_beta[sl] - mean * g;
+      if (blockIdx.x == 0 && a.tr_run_mean) {
+        const float unbias = Mtot > 1 ? (float)Mtot / (float)(Mtot - 1) : 1.f, mom = a.tr_momentum;
+        a.tr_run_mean[c] = (1.f - mom) * a.tr_run_mean[c] + mom * mean;
+        a.tr_run_var[c] = (1.f - mom) * a.tr_run_var[c] + mom * (float)var * unbias;
+      }
+    } else {
+      const double t1 = tot[WQ ? 2 : 0], t2 = tot[WQ ? 3 : 1];
+      const float invM = (float)invMd;
+      const float b1 = (float)t1;
+      const float b2 = is * (float)(t2 - md * t1);     // sum g*xhat from sum g*x and sum g, the difference in double
+      const float k1 = b1 * invM, k2 = b2 * invM;
+      B = -g * k2 * is;
+      C = -g * k1 + g * k2 * is * mean;
+      if (blockIdx.x == 0) {
+        a.tr_dbeta[c] = b1;
+        a.tr_dgamma[c] = b2;
+      }
+    }
+    coef[c] = A; coef[CI + c] = B; coef[2 * CI + c] = C;
   }
 
   __builtin_amdgcn_s_waitcnt(0);   // this wave's loads have landed (raw patches in LDS, filter in registers)
