@@ -46,18 +46,19 @@ int fdgk_sums_read(const void* sums, int c, double* host_out, void* hip_stream);
 int fdgk_conv_fwd(const void* x_b16, const void* w_b16, const float* addend_f32, float* y_f32, void* y_b16,
                   void* stats_sums, int n, int h, int w, int ci, int co, int ksize, int stride, void* hip_stream);
 
-/* y = conv3x3(relu(batchnorm(x_raw)), w), unit stride, with the batch-norm pass done on the convolution's input patch
+/* y = conv3x3(act, w), unit stride, with act = relu(batchnorm(x_raw) [+ res]) worked out on the convolution's input patch
  * on chip (Section III: a module's forward is the plain forward; this fuses two of its steps, it changes no value):
- *   act_b16 [n,h,w,ci] receives relu(gamma * (x_raw - mean) / sqrt(var + eps) + beta) in bf16, the convolution reads
- *   exactly those values; mean and the biased var come from x_sums, the complete sums array of x_raw (fdgk_bn_stats or a
- *   producing convolution's stats_sums); run_mean / run_var (optional, both or neither) take one running-statistics
- *   step with `momentum` (unbiased variance).  y_b16 [n,h,w,co]; stats_sums as fdgk_conv_fwd.
+ *   act_b16 [n,h,w,ci] receives relu(gamma * (x_raw - mean) / sqrt(var + eps) + beta [+ res_f32]) in bf16, the convolution
+ *   reads exactly those values; act_f32 (optional) receives the same in fp32; res_f32 (optional, [n,h,w,ci]) is a block's
+ *   shortcut.  mean and the biased var come from x_sums, the complete sums array of x_raw (fdgk_bn_stats or a producing
+ *   convolution's stats_sums); run_mean / run_var (optional, both or neither) take one running-statistics step with
+ *   `momentum` (unbiased variance).  y_b16 [n,h,w,co]; stats_sums as fdgk_conv_fwd.
  * Narrow layers only (ci = co in {16, 32, 64}, at most 1024 pixel tiles): fdgk_conv_fwd_bn_applies says (1 / 0); elsewhere
  * the call returns 1 (hipErrorInvalidValue) and enqueues nothing.                                                       */
-int fdgk_conv_fwd_bn_applies(int n, int h, int w, int ci, int co);
-int fdgk_conv_fwd_bn(const void* x_raw_b16, const void* x_sums, const float* gamma, const float* beta, float eps, void* act_b16,
-                     float* run_mean, float* run_var, float momentum, const void* w_b16, void* y_b16, void* stats_sums, int n,
-                     int h, int w, int ci, int co, void* hip_stream);
+int fdgk_conv_fwd_bn_applies(int n, int h, int w, int ci, int co, int with_residual);
+int fdgk_conv_fwd_bn(const void* x_raw_b16, const void* x_sums, const float* gamma, const float* beta, float eps,
+                     const float* res_f32, void* act_b16, float* act_f32, float* run_mean, float* run_var, float momentum,
+                     const void* w_b16, void* y_b16, void* stats_sums, int n, int h, int w, int ci, int co, void* hip_stream);
 
 /* Data gradient, the adjoint of fdgk_conv_fwd in x:
  *   dx[n,hi,wi,i] = sum_{o,r,q : hi = ho*s+r-p, wi = wo*s+q-p} dy[n,ho,wo,o] * w[o,r,q,i]  (+ addend)

@@ -417,16 +417,17 @@ hipError_t conv_forward(const ConvShape& c, const bf16_t* x, const bf16_t* w, co
   return launch_conv_gather(forward_args(c, x, w, addend, out_f32, out_b16, stats, stats_rep_stride), s);
 }
 
-bool conv_forward_bn_applies(const ConvShape& c) {
+bool conv_forward_bn_applies(const ConvShape& c, bool with_residual) {
   if (c.Ci != c.Cip) return false;
-  return conv_narrow_transforms(forward_args(c, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0), false, false);
+  return conv_narrow_transforms(forward_args(c, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0), with_residual ? 3 : 0);
 }
 
 hipError_t conv_forward_bn(const ConvShape& c, const ConvInputBn& bn, const bf16_t* w, const float* addend, float* out_f32,
                            bf16_t* out_b16, stat_t* stats, hipStream_t s, int stats_rep_stride) {
-  if (!bn.x_raw || !bn.sums || !bn.gamma || !bn.beta || !bn.act_out || !conv_forward_bn_applies(c)) return hipErrorInvalidValue;
+  if (!bn.x_raw || !bn.sums || !bn.gamma || !bn.beta || !bn.act_out || !conv_forward_bn_applies(c, bn.res_f32 != nullptr))
+    return hipErrorInvalidValue;
   GatherConvArgs a = forward_args(c, nullptr, w, addend, out_f32, out_b16, stats, stats_rep_stride);
-  a.tr_mode = 1; a.tr_p = bn.x_raw; a.tr_out = bn.act_out; a.tr_sums = bn.sums; a.tr_gamma = bn.gamma; a.tr_beta = bn.beta;
+  a.tr_mode = 1; a.tr_p = bn.x_raw; a.tr_q = bn.res_f32; a.tr_out = bn.act_out; a.tr_out_f32 = bn.act_out_f32; a.tr_sums = bn.sums; a.tr_gamma = bn.gamma; a.tr_beta = bn.beta;
   a.tr_run_mean = bn.run_mean; a.tr_run_var = bn.run_mean ? bn.run_var : nullptr;
   a.tr_eps = bn.eps; a.tr_momentum = bn.momentum; a.tr_rep_stride = bn.rep_stride;
   return launch_conv_narrow(a, s);
@@ -487,7 +488,7 @@ bool conv_dgrad_bn_applies(const ConvShape& c, bool g_is_f32) {
   a.OH = c.Hi; a.OW = c.Wi; a.OHf = c.Hi; a.OWf = c.Wi; a.in_stride = 1; a.out_stride = 1; a.ntaps = 9;
   for (int r = 0; r < 3; ++r)
     for (int q = 0; q < 3; ++q) a.tap[r * 3 + q] = pack_tap(1 - r, 1 - q, r * 3 + q);
-  return conv_narrow_transforms(a, g_is_f32, true);
+  return conv_narrow_transforms(a, g_is_f32 ? 2 : 1);
 }
 
 hipError_t conv_dgrad_after_bn(const ConvShape& c, const ConvInputBnBwd& bn, const bf16_t* wt, const float* addend,
@@ -543,7 +544,7 @@ static hipError_t conv_dgrad_impl(const ConvShape& c, const bf16_t* dy, const bf
     }
     if (bn) {   // the batch-norm backward that produces dy, on the patch (narrow kernel)
       if (!bn->g || !bn->x || !bn->sums || !bn->bsums || !bn->gamma || !bn->dgamma || !bn->dbeta || !bn->dy_out ||
-          !conv_narrow_transforms(a, bn->g_is_f32 != 0, true))
+          !conv_narrow_transforms(a, bn->g_is_f32 ? 2 : 1))
         return hipErrorInvalidValue;
       a.in = nullptr;
       a.tr_mode = 2; a.tr_p = bn->g; a.tr_p_f32 = bn->g_is_f32 ? 1 : 0; a.tr_q = bn->x; a.tr_out = bn->dy_out;

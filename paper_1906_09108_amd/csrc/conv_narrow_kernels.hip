@@ -340,8 +340,11 @@ hipError_t run_narrow_j(const GatherConvArgs& a, hipStream_t s) {
 // gradient) reads later.  Halo rows are transformed by every workgroup that needs them; the zero area stays zero, so
 // padding is zero AFTER the transform, as it must be.  One tile per workgroup; the rest (filter in registers, MFMAs,
 // output stage) is conv_narrow_kernel's.
-template <int CI, int NB, int WN, int J, bool PF32, bool WQ>
+// VAR: 0 forward batch norm + ReLU of p (bf16);  1 / 2 batch-norm backward of p (bf16 / fp32) with q;  3 forward batch
+// norm of p (bf16) + fp32 residual r (tr_q) + ReLU.  The forward forms also write y in fp32 where tr_out_f32 is given.
+template <int CI, int NB, int WN, int J, int VAR>
 __global__ __launch_bounds__(256) void conv_narrow_tr_kernel(GatherConvArgs a, NarrowLaunch L) {
+  constexpr bool PF32 = VAR == 2, WQ = VAR == 1 || VAR == 2, WR = VAR == 3;
   constexpr int WM = 4 / WN, TP = 16 * J * WM, CO = 16 * NB * WN;
   constexpr int U = CI / 8, ROWB = CI * 2;
   constexpr int S = (9 * CI + 31) / 32;
@@ -405,6 +408,15 @@ __global__ __launch_bounds__(256) void conv_narrow_tr_kernel(GatherConvArgs a, N
         int q = m0 - W - 1 + r;
         q = q < 0 ? 0 : (q >= Mtot ? Mtot - 1 : q);
         narrow_dma16(reinterpret_cast<const char*>(a.tr_q) + (size_t)q * ROWB + uq * 16, rawq + (size_t)base * 16);
+      }
+    }
+    if (WR) {   // the residual: fp32, two units per 8 channels
+      for (int base = wave * 64; base < 2 * units; base += 256) {
+        const int pos = base + lane;
+        const int r = pos / (2 * U), ur = pos % (2 * U);
+        int q = m0 - W - 1 + r;
+        q = q < 0 ? 0 : (q >= Mtot ? Mtot - 1 : q);
+        narrow_dma16(reinterpret_cast<const char*>(a.tr_q) + (size_t)q * (CI * 4) + ur * 16, rawq + (size_t)base * 16);
       }
     }
   }
@@ -535,13 +547,26 @@ __global__ __launch_bounds__(256) void conv_narrow_tr_kernel(GatherConvArgs a, N
       for (int i = 0; i < 8; ++i) y[i] = Av[i] * pv[i] + (Bv[i] * qv[i] + Cv[i]);
     } else {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) y[i] = fmaxf(pv[i] * Av[i] + Cv[i], 0.f);
+      for (int i = 0; i < 8; ++i) y[i] = pv[i] * Av[i] + Cv[i];
+      if (WR) {
+        const float4 r0 = *reinterpret_cast<const float4*>(rawq + ((size_t)r * 2 * U + 2 * u) * 16);
+        const float4 r1 = *reinterpret_cast<const float4*>(rawq + ((size_t)r * 2 * U + 2 * u + 1) * 16);
+        y[0] += r0.x; y[1] += r0.y; y[2] += r0.z; y[3] += r0.w; y[4] += r1.x; y[5] += r1.y; y[6] += r1.z; y[7] += r1.w;
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) y[i] = fmaxf(y[i], 0.f);
     }
     const uint4 packed = make_uint4(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]), pack_bf16x2(y[6], y[7]));
     *reinterpret_cast<uint4*>(patch + (size_t)pos * 16) = packed;
     const int pl = r - (W + 1);
-    if (pl >= 0 && pl < TP && m0 + pl < Mtot)
+    if (pl >= 0 && pl < TP && m0 + pl < Mtot) {
       *reinterpret_cast<uint4*>(a.tr_out + (size_t)(m0 + pl) * CI + 8 * u) = packed;
+      if (!WQ && a.tr_out_f32) {
+        float* o = a.tr_out_f32 + (size_t)(m0 + pl) * CI + 8 * u;
+        *reinterpret_cast<float4*>(o) = make_float4(y[0], y[1], y[2], y[3]);
+        *reinterpret_cast<float4*>(o + 4) = make_float4(y[4], y[5], y[6], y[7]);
+      }
+    }
   }
   __syncthreads();
 
@@ -570,37 +595,38 @@ __global__ __launch_bounds__(256) void conv_narrow_tr_kernel(GatherConvArgs a, N
 }
 
 // LDS of the kernel above for `units` units of patch
-static size_t narrow_tr_lds(int units, int CI, bool p_f32, bool with_q) {
-  return (size_t)units * 16 + 128 + (size_t)12 * CI + (size_t)units * (p_f32 ? 32 : 16) + (with_q ? (size_t)units * 16 : 0);
+static size_t narrow_tr_lds(int units, int CI, int var) {
+  return (size_t)units * 16 + 128 + (size_t)12 * CI + (size_t)units * (var == 2 ? 32 : 16) +
+         ((var == 1 || var == 2) ? (size_t)units * 16 : (var == 3 ? (size_t)units * 32 : 0));
 }
 constexpr int kNarrowTrMaxTiles = 1024;   // beyond that a workgroup per tile re-reads the filter too often: the looped kernel runs
 constexpr size_t kNarrowTrMaxLds = 150 * 1024;
 
-template <int CI, int NB, int WN, int J, bool PF32, bool WQ>
+template <int CI, int NB, int WN, int J, int VAR>
 hipError_t run_narrow_tr(const GatherConvArgs& a, hipStream_t s) {
   constexpr int WM = 4 / WN, TP = 16 * J * WM, U = CI / 8;
   const int Mtot = a.N * a.OH * a.OW;
   const int rows = TP + 2 * a.Wi + 2;
   const int units = (rows * U + 255) / 256 * 256;
-  const size_t lds = narrow_tr_lds(units, CI, PF32, WQ);
+  const size_t lds = narrow_tr_lds(units, CI, VAR);
   const int ntiles = (Mtot + TP - 1) / TP;
   if (lds > kNarrowTrMaxLds || ntiles > kNarrowTrMaxTiles) return hipErrorInvalidValue;
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_narrow_tr_kernel<CI, NB, WN, J, PF32, WQ>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_narrow_tr_kernel<CI, NB, WN, J, VAR>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kNarrowTrMaxLds);
     if (e != hipSuccess) return e;
     configured = true;
   }
   static char name[80];
-  if (!name[0]) snprintf(name, sizeof(name), "conv_narrow_tr_kernel<%d, %d, %d, %d, %s>", CI, NB, WN, J, WQ ? (PF32 ? "bn bwd f32" : "bn bwd") : "bn fwd");
+  if (!name[0]) snprintf(name, sizeof(name), "conv_narrow_tr_kernel<%d, %d, %d, %d, %s>", CI, NB, WN, J, VAR == 0 ? "bn fwd" : (VAR == 1 ? "bn bwd" : (VAR == 2 ? "bn bwd f32" : "bn fwd + res")));
   note_kernel(name);
   NarrowLaunch L;
   L.units = units;
   L.magic_w = ((1ull << 40) + a.Wi - 1) / a.Wi;
   L.magic_h = ((1ull << 40) + a.Hi - 1) / a.Hi;
   L.same_masks = 0;
-  hipLaunchKernelGGL((conv_narrow_tr_kernel<CI, NB, WN, J, PF32, WQ>), dim3(ntiles), dim3(256), lds, s, a, L);
+  hipLaunchKernelGGL((conv_narrow_tr_kernel<CI, NB, WN, J, VAR>), dim3(ntiles), dim3(256), lds, s, a, L);
   return hipGetLastError();
 }
 
@@ -608,19 +634,19 @@ hipError_t run_narrow_tr(const GatherConvArgs& a, hipStream_t s) {
 template <int WM>
 static int narrow_j_for(int Mtot) { return Mtot >= 512 * 64 * WM ? 4 : (Mtot >= 512 * 32 * WM ? 2 : 1); }
 
-template <int CI, int NB, int WN, bool PF32, bool WQ>
+template <int CI, int NB, int WN, int VAR>
 hipError_t run_narrow_tr_j(const GatherConvArgs& a, hipStream_t s) {
   switch (narrow_j_for<4 / WN>(a.N * a.OH * a.OW)) {
-    case 4: return run_narrow_tr<CI, NB, WN, 4, PF32, WQ>(a, s);
-    case 2: return run_narrow_tr<CI, NB, WN, 2, PF32, WQ>(a, s);
-    default: return run_narrow_tr<CI, NB, WN, 1, PF32, WQ>(a, s);
+    case 4: return run_narrow_tr<CI, NB, WN, 4, VAR>(a, s);
+    case 2: return run_narrow_tr<CI, NB, WN, 2, VAR>(a, s);
+    default: return run_narrow_tr<CI, NB, WN, 1, VAR>(a, s);
   }
 }
-template <bool PF32, bool WQ>
+template <int VAR>
 hipError_t run_narrow_tr_c(const GatherConvArgs& a, hipStream_t s) {
-  if (a.Ci == 16) return run_narrow_tr_j<16, 1, 1, PF32, WQ>(a, s);
-  if (a.Ci == 32) return run_narrow_tr_j<32, 2, 1, PF32, WQ>(a, s);
-  return run_narrow_tr_j<64, 2, 2, PF32, WQ>(a, s);
+  if (a.Ci == 16) return run_narrow_tr_j<16, 1, 1, VAR>(a, s);
+  if (a.Ci == 32) return run_narrow_tr_j<32, 2, 1, VAR>(a, s);
+  return run_narrow_tr_j<64, 2, 2, VAR>(a, s);
 }
 
 
@@ -868,25 +894,31 @@ bool conv_narrow_applies(const GatherConvArgs& a) {
   return true;
 }
 
-bool conv_narrow_transforms(const GatherConvArgs& a, bool p_f32, bool with_q) {
+// var as the kernel's VAR
+bool conv_narrow_transforms(const GatherConvArgs& a, int var) {
   if (!conv_narrow_applies(a) || (a.Ci != 16 && a.Ci != 32 && a.Ci != 64)) return false;
   const int Mtot = a.N * a.OH * a.OW;
   const int WM = a.Ci == 64 ? 2 : 4;
   const int J = Mtot >= 512 * 64 * WM ? 4 : (Mtot >= 512 * 32 * WM ? 2 : 1);
   const int TP = 16 * J * WM;
   const int units = ((TP + 2 * a.Wi + 2) * (a.Ci / 8) + 255) / 256 * 256;
-  return Mtot > 0 && (Mtot + TP - 1) / TP <= kNarrowTrMaxTiles && narrow_tr_lds(units, a.Ci, p_f32, with_q) <= kNarrowTrMaxLds;
+  return Mtot > 0 && (Mtot + TP - 1) / TP <= kNarrowTrMaxTiles && var >= 0 && var <= 3 && narrow_tr_lds(units, a.Ci, var) <= kNarrowTrMaxLds;
 }
 
 hipError_t launch_conv_narrow(const GatherConvArgs& a, hipStream_t s) {
   if (!conv_narrow_applies(a) || a.N * a.OH * a.OW <= 0) return hipErrorInvalidValue;
   if (a.tr_mode != 0) {
     const bool wq = a.tr_mode == 2;
+    const int var = wq ? (a.tr_p_f32 ? 2 : 1) : (a.tr_q ? 3 : 0);   // forward form: tr_q, if given, is the fp32 residual
     if ((a.tr_mode != 1 && a.tr_mode != 2) || !a.tr_p || !a.tr_out || !a.tr_sums || !a.tr_gamma || (wq && (!a.tr_q || !a.tr_bsums || !a.tr_dgamma || !a.tr_dbeta)) ||
-        (!wq && (!a.tr_beta || a.tr_p_f32)) || !conv_narrow_transforms(a, a.tr_p_f32 != 0, wq))
+        (!wq && (!a.tr_beta || a.tr_p_f32)) || !conv_narrow_transforms(a, var))
       return hipErrorInvalidValue;
-    if (!wq) return run_narrow_tr_c<false, false>(a, s);
-    return a.tr_p_f32 ? run_narrow_tr_c<true, true>(a, s) : run_narrow_tr_c<false, true>(a, s);
+    switch (var) {
+      case 0: return run_narrow_tr_c<0>(a, s);
+      case 1: return run_narrow_tr_c<1>(a, s);
+      case 2: return run_narrow_tr_c<2>(a, s);
+      default: return run_narrow_tr_c<3>(a, s);
+    }
   }
   if (a.Ci == 8) return a.Co == 16 ? run_narrow_j<8, 1, 1>(a, s) : (a.Co == 32 ? run_narrow_j<8, 2, 1>(a, s) : run_narrow_j<8, 4, 1>(a, s));
   if (a.Ci == 16) return run_narrow_j<16, 1, 1>(a, s);

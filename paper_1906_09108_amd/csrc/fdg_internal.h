@@ -111,14 +111,17 @@ struct GatherConvArgs {
   // both [N, Hi, Wi, Ci], with per-channel coefficients from batch-norm sums; every workgroup also writes the y of its
   // own pixels to tr_out (bf16 [N, Hi, Wi, Ci]), which is then what a batch-norm pass of its own would have left.
   //   mode 1: forward batch norm + ReLU of p.  A = gamma * invstd, B = 0, C = beta - mean * A from tr_sums (sums of p);
-  //           act = max(., 0); tr_run_mean / tr_run_var (optional) take one running-statistics step.
+  //           act = max(., 0); tr_run_mean / tr_run_var (optional) take one running-statistics step.  With tr_q given, tr_q
+  //           is an fp32 residual [N, Hi, Wi, Ci] added before the ReLU (the end of a basic block); tr_out_f32 (optional)
+  //           receives y in fp32 as well (the residual stream).
   //   mode 2: backward of the batch norm whose input was q, applied to the gated gradient p.  A, B, C from tr_sums
   //           (forward sums of q) and tr_bsums (sum p, sum p*q) as in BnBwdArgs with raw_sums; no act; tr_dgamma and
   //           tr_dbeta are written.
   int tr_mode, tr_p_f32;
   const void* tr_p;
-  const bf16_t* tr_q;
+  const void* tr_q;
   bf16_t* tr_out;
+  float* tr_out_f32;
   const stat_t* tr_sums;
   const stat_t* tr_bsums;
   const float* tr_gamma;
@@ -132,7 +135,7 @@ struct GatherConvArgs {
 };
 // whether the narrow kernel takes this layer with an input transform (a geometry conv_narrow_applies accepts, real input
 // channels, one tile per workgroup, LDS for the raw patches)
-bool conv_narrow_transforms(const GatherConvArgs& a, bool p_f32, bool with_q);
+bool conv_narrow_transforms(const GatherConvArgs& a, int var);   // var: 0 mode 1; 1 / 2 mode 2 with bf16 / fp32 p; 3 mode 1 with a residual
 hipError_t launch_conv_gather(const GatherConvArgs& a, hipStream_t s);
 // narrow layers (16 / 32 / 64 channels in and out, 3x3, unit stride): whole patch and whole filter on chip
 bool conv_narrow_applies(const GatherConvArgs& a);
@@ -175,6 +178,8 @@ hipError_t conv_forward(const ConvShape& c, const bf16_t* x, const bf16_t* w, co
 // GatherConvArgs::tr_mode = 1): act_out receives relu(batchnorm(x_raw)) in bf16 as a pass of its own would have written
 // it; run_mean / run_var (optional) take one running-statistics step.  conv_forward_bn_applies says where.
 struct ConvInputBn {
+  const float* res_f32;  // optional [N, Hi, Wi, Cip]: added to the normalised value before the ReLU
+  float* act_out_f32;    // optional [N, Hi, Wi, Cip]: the activation in fp32 as well
   const bf16_t* x_raw;   // [N, Hi, Wi, Cip] the batch norm's input
   const stat_t* sums;    // its sums array (sum, sum of squares), complete
   const float* gamma;
@@ -185,7 +190,7 @@ struct ConvInputBn {
   float eps, momentum;
   int rep_stride;        // stat_t elements between the copies of sums (0: one copy)
 };
-bool conv_forward_bn_applies(const ConvShape& c);
+bool conv_forward_bn_applies(const ConvShape& c, bool with_residual = false);
 hipError_t conv_forward_bn(const ConvShape& c, const ConvInputBn& bn, const bf16_t* w, const float* addend, float* out_f32,
                            bf16_t* out_b16, stat_t* stats, hipStream_t s, int stats_rep_stride = 0);
 // A data gradient whose input dy is the apply half of a batch-norm backward, done on the patch in LDS (narrow layers,

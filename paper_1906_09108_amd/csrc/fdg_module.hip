@@ -576,16 +576,21 @@ hipError_t mconv_forward(const fdg_module* m, const ConvInfo& c, const bf16_t* x
 }
 // relu(batchnorm_b(x_raw)) -> act_out and the convolution of it, in one launch where the narrow kernel takes the batch-norm
 // pass on its patch (conv_forward_bn_applies); false: the caller runs the two launches
-bool forward_bn_fuses(const ConvInfo& c, const BnInfo& b) {
-  return b.C == c.sh.Cip && (long long)b.M == (long long)c.sh.N * c.sh.Hi * c.sh.Wi && conv_forward_bn_applies(c.sh);
+bool forward_bn_fuses(const ConvInfo& c, const BnInfo& b, bool with_residual = false) {
+  return b.C == c.sh.Cip && (long long)b.M == (long long)c.sh.N * c.sh.Hi * c.sh.Wi && conv_forward_bn_applies(c.sh, with_residual);
 }
+// res (optional, fp32) is added before the ReLU and act_out_f32 (optional) receives the activation in fp32: the end of the
+// layer BELOW (its last batch norm, shortcut and ReLU) done on the patch of this layer's first convolution
 hipError_t mconv_forward_after_bn(const fdg_module* m, const SlotView& v, const ConvInfo& c, const BnInfo& b, const bf16_t* x_raw,
-                                  bf16_t* act_out, const bf16_t* w, bf16_t* out_b16, stat_t* stats, bool replayed, hipStream_t s) {
+                                  bf16_t* act_out, const bf16_t* w, bf16_t* out_b16, stat_t* stats, bool replayed, hipStream_t s,
+                                  const float* res = nullptr, float* act_out_f32 = nullptr) {
   ConvInputBn bn{};
+  bn.res_f32 = res; bn.act_out_f32 = act_out_f32;
   bn.x_raw = x_raw; bn.sums = v.sums(b); bn.gamma = v.snap(b.gamma_off); bn.beta = v.snap(b.beta_off); bn.act_out = act_out;
   if (!replayed) { bn.run_mean = m->running() + b.stat_off; bn.run_var = m->running() + b.stat_off + b.C; }
   bn.eps = m->p.d.bn_eps; bn.momentum = m->p.d.bn_momentum; bn.rep_stride = m->p.stat_rep;
-  const double bytes = 2 * conv_in_elems(c.sh) * 2 + 2 * conv_w_elems(c.sh) + conv_out_elems(c.sh) * (out_b16 ? 2 : 0);
+  const double bytes = conv_in_elems(c.sh) * (2 + 2 + (res ? 4 : 0) + (act_out_f32 ? 4 : 0)) + 2 * conv_w_elems(c.sh) +
+                       conv_out_elems(c.sh) * (out_b16 ? 2 : 0);
   ProfScope ps(m, PC_CONV_FWD, conv_flops(c.sh), bytes, s);
   const hipError_t e = conv_forward_bn(c.sh, bn, w, nullptr, nullptr, out_b16, stats, s, m->p.stat_rep);
   ps.label(c.sh);
@@ -819,20 +824,45 @@ fdg_status forward_pass(fdg_module* m, const SlotView& v, const float* x_dev, fl
                               p.Cp_in, 1.f, s));
   const bf16_t* cur_b = v.xin();
   bool stats_ready = false;   // the sums of this layer's leading BN were taken by the producer of its input
+  // The last pass of a layer (batch norm [+ shortcut] + ReLU into the fp32 stream and its bf16 copy) is left to the first
+  // convolution of the layer ABOVE where that is a basic block whose narrow kernel takes it on its patch: `pend` is that pass,
+  // owed from the end of one iteration to the start of the next.
+  struct { bool owed = false; const BnInfo* b = nullptr; const bf16_t* x_raw = nullptr; const float* res = nullptr; size_t layer = 0; } pend;
+  auto above_takes = [&](size_t li, const BnInfo& b, bool with_res) {
+    if (li + 1 >= p.L.size()) return false;
+    const LayerPlan& up = p.L[li + 1];
+    return up.kind == FDG_BASIC_POSTACT && forward_bn_fuses(p.convs[up.conv[0]], b, with_res);
+  };
   for (size_t li = 0; li < p.L.size(); ++li) {
     const LayerPlan& L = p.L[li];
     const int nxt = cur ^ 1;
     bool next_ready = false;
+    bool owes = false;
     if (L.kind == FDG_STEM_CONV_BN_RELU) {
       const ConvInfo& c0 = p.convs[L.conv[0]];
       const BnInfo& b0 = p.bns[L.bn[0]];
       FDG_TRY(mconv_forward(m, c0, cur_b, v.W(c0), nullptr, nullptr, v.act(L.act[0]), v.sums(b0), s));
-      FDG_TRY(bn_apply(m, v, b0, v.act(L.act[0]), nullptr, nullptr, nullptr, m->S(nxt), v.act(L.out_b), replayed, s));
+      if (above_takes(li, b0, false)) {
+        pend.owed = owes = true; pend.b = &b0; pend.x_raw = v.act(L.act[0]); pend.res = nullptr; pend.layer = li;
+      } else {
+        FDG_TRY(bn_apply(m, v, b0, v.act(L.act[0]), nullptr, nullptr, nullptr, m->S(nxt), v.act(L.out_b), replayed, s));
+      }
     } else if (L.kind == FDG_BASIC_POSTACT) {
       const ConvInfo &c1 = p.convs[L.conv[0]], &c2 = p.convs[L.conv[1]];
       const BnInfo &b1 = p.bns[L.bn[0]], &b2 = p.bns[L.bn[1]];
       bf16_t *t_c1 = v.act(L.act[0]), *t_a1 = v.act(L.act[1]), *t_c2 = v.act(L.act[2]);
-      FDG_TRY(mconv_forward(m, c1, cur_b, v.W(c1), nullptr, nullptr, t_c1, v.sums(b1), s));
+      if (pend.owed) {
+        // this layer's input (fp32 stream S(cur) and its bf16 copy cur_b) is written here, by the convolution that reads it
+        const LayerPlan& below = p.L[pend.layer];
+        FDG_TRY(mconv_forward_after_bn(m, v, c1, *pend.b, pend.x_raw, v.act(below.out_b), v.W(c1), t_c1, v.sums(b1), replayed, s,
+                                       pend.res, m->S(cur)));
+        if (m->trace && !replayed)
+          FDG_TRY(hipMemcpyAsync(m->trace + p.tr_fwd[pend.layer], m->S(cur), (size_t)N * below.Ho * below.Wo * below.c_out * 4,
+                                 hipMemcpyDeviceToDevice, s));
+        pend.owed = false;
+      } else {
+        FDG_TRY(mconv_forward(m, c1, cur_b, v.W(c1), nullptr, nullptr, t_c1, v.sums(b1), s));
+      }
       if (forward_bn_fuses(c2, b1)) {   // BN1 + ReLU on the patch of the second convolution
         FDG_TRY(mconv_forward_after_bn(m, v, c2, b1, t_c1, t_a1, v.W(c2), t_c2, v.sums(b2), replayed, s));
       } else {
@@ -845,6 +875,8 @@ fdg_status forward_pass(fdg_module* m, const SlotView& v, const float* x_dev, fl
         bf16_t* t_p = v.act(L.act[3]);
         FDG_TRY(mconv_forward(m, cp, cur_b, v.W(cp), nullptr, nullptr, t_p, v.sums(bp), s));
         FDG_TRY(bn_apply(m, v, b2, t_c2, nullptr, &bp, t_p, m->S(nxt), v.act(L.out_b), replayed, s));
+      } else if (above_takes(li, b2, true)) {
+        pend.owed = owes = true; pend.b = &b2; pend.x_raw = t_c2; pend.res = m->S(cur); pend.layer = li;
       } else {
         FDG_TRY(bn_apply(m, v, b2, t_c2, m->S(cur), nullptr, nullptr, m->S(nxt), v.act(L.out_b), replayed, s));
       }
@@ -924,7 +956,7 @@ fdg_status forward_pass(fdg_module* m, const SlotView& v, const float* x_dev, fl
       FDG_TRY(launch_softmax_ce(v.logits(), v.labels(), y_dev, v.dl(), N, J, s));
       break;
     }
-    if (m->trace && !replayed)
+    if (m->trace && !replayed && !owes)
       FDG_TRY(hipMemcpyAsync(m->trace + p.tr_fwd[li], m->S(nxt), (size_t)N * L.Ho * L.Wo * L.c_out * 4, hipMemcpyDeviceToDevice, s));
     cur = nxt;
     cur_b = v.act(L.out_b);

@@ -59,18 +59,19 @@ int fdgk_conv_fwd(const void* x_b16, const void* w_b16, const float* addend_f32,
                            static_cast<bf16_t*>(y_b16), static_cast<stat_t*>(stats_sums), st(hip_stream));
 }
 
-int fdgk_conv_fwd_bn_applies(int n, int h, int w, int ci, int co) {
+int fdgk_conv_fwd_bn_applies(int n, int h, int w, int ci, int co, int with_residual) {
   ConvShape c;
-  return conv_shape(c, n, h, w, ci, co, 3, 1) && conv_forward_bn_applies(c) ? 1 : 0;
+  return conv_shape(c, n, h, w, ci, co, 3, 1) && conv_forward_bn_applies(c, with_residual != 0) ? 1 : 0;
 }
 
-int fdgk_conv_fwd_bn(const void* x_raw_b16, const void* x_sums, const float* gamma, const float* beta, float eps, void* act_b16,
-                     float* run_mean, float* run_var, float momentum, const void* w_b16, void* y_b16, void* stats_sums, int n,
-                     int h, int w, int ci, int co, void* hip_stream) {
+int fdgk_conv_fwd_bn(const void* x_raw_b16, const void* x_sums, const float* gamma, const float* beta, float eps,
+                     const float* res_f32, void* act_b16, float* act_f32, float* run_mean, float* run_var, float momentum,
+                     const void* w_b16, void* y_b16, void* stats_sums, int n, int h, int w, int ci, int co, void* hip_stream) {
   ConvShape c;
   if (!x_raw_b16 || !x_sums || !gamma || !beta || !act_b16 || !w_b16 || !y_b16 || !conv_shape(c, n, h, w, ci, co, 3, 1))
     return (int)hipErrorInvalidValue;
   ConvInputBn bn{};
+  bn.res_f32 = res_f32; bn.act_out_f32 = act_f32;
   bn.x_raw = static_cast<const bf16_t*>(x_raw_b16); bn.sums = static_cast<const stat_t*>(x_sums); bn.gamma = gamma; bn.beta = beta;
   bn.act_out = static_cast<bf16_t*>(act_b16); bn.run_mean = run_mean; bn.run_var = run_var; bn.eps = eps; bn.momentum = momentum;
   return (int)conv_forward_bn(c, bn, static_cast<const bf16_t*>(w_b16), nullptr, nullptr, static_cast<bf16_t*>(y_b16),

@@ -21,10 +21,10 @@ def _lib():
         vp, i, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
         lib.fdgk_conv_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
         lib.fdgk_conv_dgrad.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
-        lib.fdgk_conv_fwd_bn_applies.argtypes = [i, i, i, i, i]
+        lib.fdgk_conv_fwd_bn_applies.argtypes = [i, i, i, i, i, i]
         lib.fdgk_conv_dgrad_bn_applies.argtypes = [i, i, i, i, i, i]
         lib.fdgk_conv_dgrad_bn.argtypes = [vp, i, vp, vp, vp, vp, f, vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, vp]
-        lib.fdgk_conv_fwd_bn.argtypes = [vp, vp, vp, vp, f, vp, vp, vp, f, vp, vp, vp, i, i, i, i, i, vp]
+        lib.fdgk_conv_fwd_bn.argtypes = [vp, vp, vp, vp, f, vp, vp, vp, vp, vp, f, vp, vp, vp, i, i, i, i, i, vp]
         lib.fdgk_conv_dgrad_gated.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
         lib.fdgk_conv_dgrad_feeding_next.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
         lib.fdgk_conv_dgrad_gates.argtypes = [i, i, i, i, i, i, i]
@@ -94,15 +94,15 @@ def fdgk_conv_fwd(x_b16, w_b16, addend_f32, y_f32, y_b16, stats_f32, n, h, w, ci
                              n, h, w, ci, co, ksize, stride, _stream_handle(stream)), "fdgk_conv_fwd")
 
 
-def fdgk_conv_fwd_bn_applies(n, h, w, ci, co) -> bool:
-    return bool(_lib().fdgk_conv_fwd_bn_applies(n, h, w, ci, co))
+def fdgk_conv_fwd_bn_applies(n, h, w, ci, co, with_residual=False) -> bool:
+    return bool(_lib().fdgk_conv_fwd_bn_applies(n, h, w, ci, co, 1 if with_residual else 0))
 
 
-def fdgk_conv_fwd_bn(x_raw_b16, x_sums, gamma, beta, eps, act_b16, run_mean, run_var, momentum, w_b16, y_b16, stats_sums, n, h, w,
-                     ci, co, stream=None):
-    _ok(_lib().fdgk_conv_fwd_bn(_ptr(x_raw_b16), _ptr(x_sums), _ptr(gamma), _ptr(beta), eps, _ptr(act_b16), _ptr(run_mean),
-                                _ptr(run_var), momentum, _ptr(w_b16), _ptr(y_b16), _ptr(stats_sums), n, h, w, ci, co,
-                                _stream_handle(stream)), "fdgk_conv_fwd_bn")
+def fdgk_conv_fwd_bn(x_raw_b16, x_sums, gamma, beta, eps, res_f32, act_b16, act_f32, run_mean, run_var, momentum, w_b16, y_b16,
+                     stats_sums, n, h, w, ci, co, stream=None):
+    _ok(_lib().fdgk_conv_fwd_bn(_ptr(x_raw_b16), _ptr(x_sums), _ptr(gamma), _ptr(beta), eps, _ptr(res_f32), _ptr(act_b16),
+                                _ptr(act_f32), _ptr(run_mean), _ptr(run_var), momentum, _ptr(w_b16), _ptr(y_b16), _ptr(stats_sums),
+                                n, h, w, ci, co, _stream_handle(stream)), "fdgk_conv_fwd_bn")
 
 
 def fdgk_conv_dgrad_bn_applies(n, h, w, ci, co, g_is_f32) -> bool:

@@ -413,16 +413,18 @@ FWD_BN_CASES = [  # (n, h, w, c): narrow layers, unit stride
 ]
 
 
+@pytest.mark.parametrize("with_res", [False, True])
 @pytest.mark.parametrize("case", FWD_BN_CASES)
-def test_convolution_with_batch_norm_on_its_patch(case):
-    """fdgk_conv_fwd_bn: act = relu(batchnorm(x_raw)) written in bf16 and y = conv(act, w).  Reference: the oracle's batch norm
-    (fp32 definition) on x_raw, ReLU, then the oracle's convolution of the bf16 values the kernel wrote; and the fused launch
-    against the two launches it replaces (fdgk_bn_apply, then fdgk_conv_fwd), which must agree to a bf16 step of act."""
+def test_convolution_with_batch_norm_on_its_patch(case, with_res):
+    """fdgk_conv_fwd_bn: act = relu(batchnorm(x_raw) [+ res]) written in bf16 (and fp32) and y = conv(act, w).  Reference: the
+    oracle's batch norm (fp32 definition) on x_raw, the shortcut, ReLU, then the oracle's convolution of the bf16 values the
+    kernel wrote; and the fused launch against the two launches it replaces (fdgk_bn_apply, then fdgk_conv_fwd), which must
+    agree to a bf16 step of act."""
     from paper_1906_09108_amd import kernels as K
     t = _torch()
     n, h, w, c = case
-    print("conv_fwd_bn", case, flush=True)
-    assert K.fdgk_conv_fwd_bn_applies(n, h, w, c, c)
+    print("conv_fwd_bn", case, with_res, flush=True)
+    assert K.fdgk_conv_fwd_bn_applies(n, h, w, c, c, with_res)
     r = np.random.default_rng(31 + n + c)
     eps, mom = 1e-5, 0.1
     m = n * h * w
@@ -431,7 +433,9 @@ def test_convolution_with_batch_norm_on_its_patch(case):
     gamma = (1 + 0.2 * r.standard_normal(c)).astype(np.float32)
     beta = (0.2 * r.standard_normal(c)).astype(np.float32)
     y_bn, mean, var, invstd = K32.bn_fwd(x, gamma, beta, eps)
-    act_ref = np.maximum(y_bn.astype(np.float64), 0)
+    res = r.standard_normal((n, c, h, w)).astype(np.float32) if with_res else None
+    act_ref = np.maximum(y_bn.astype(np.float64) + (res if with_res else 0.0), 0)
+    resd = to_dev_nhwc_f32(res) if with_res else None
     xd = to_dev_nhwc_b16(x)
     sums = K.new_sums(c)
     K.fdgk_bn_stats(xd.reshape(m, c), sums, m, c)
@@ -440,12 +444,14 @@ def test_convolution_with_batch_norm_on_its_patch(case):
     rm0, rv0 = r.standard_normal(c).astype(np.float32), (1 + r.random(c)).astype(np.float32)
     rm, rv = t.from_numpy(rm0.copy()).cuda(), t.from_numpy(rv0.copy()).cuda()
     act = t.full((n, h, w, c), float("nan"), dtype=t.bfloat16, device="cuda")
+    act32 = t.full((n, h, w, c), float("nan"), dtype=t.float32, device="cuda")
     y16 = t.full((n, h, w, c), float("nan"), dtype=t.bfloat16, device="cuda")
     st = K.new_sums(c)
-    K.fdgk_conv_fwd_bn(xd, sums, gd, bd, eps, act, rm, rv, mom, wd, y16, st, n, h, w, c, c)
+    K.fdgk_conv_fwd_bn(xd, sums, gd, bd, eps, resd, act, act32, rm, rv, mom, wd, y16, st, n, h, w, c, c)
     t.cuda.synchronize()
     act_got = nhwc_to_nchw(act)
     assert rel(act_got, act_ref) <= B16_TOL
+    assert rel(nhwc_to_nchw(act32), act_ref) <= F32_TOL
     assert np.all(act_got >= 0)
     # the convolution of exactly the values written
     y_ref = K32.conv_fwd(act_got.astype(np.float32), wt, 1, 1).astype(np.float64)
@@ -462,7 +468,7 @@ def test_convolution_with_batch_norm_on_its_patch(case):
     # the two launches it replaces
     act2 = t.empty((m, c), dtype=t.bfloat16, device="cuda")
     y2 = t.empty((n, h, w, c), dtype=t.bfloat16, device="cuda")
-    K.fdgk_bn_apply(xd.reshape(m, c), sums, gd, bd, None, None, act2, m, c, eps, 1)
+    K.fdgk_bn_apply(xd.reshape(m, c), sums, gd, bd, resd.reshape(m, c) if with_res else None, None, act2, m, c, eps, 1)
     K.fdgk_conv_fwd(act2, wd, None, None, y2, None, n, h, w, c, c, 3, 1)
     t.cuda.synchronize()
     assert rel(act.to(t.float32).reshape(m, c).cpu().numpy(), act2.to(t.float32).cpu().numpy().astype(np.float64)) <= 2.0 ** -8
@@ -539,6 +545,7 @@ def test_conv_fwd_bn_refuses_what_it_does_not_cover():
     assert not K.fdgk_conv_fwd_bn_applies(2, 8, 8, 128, 128)      # wide layer
     assert not K.fdgk_conv_fwd_bn_applies(2, 8, 8, 16, 32)        # channels change
     assert not K.fdgk_conv_fwd_bn_applies(128, 64, 64, 64, 64)    # more tiles than a workgroup each may take
+    assert not K.fdgk_conv_fwd_bn_applies(128, 64, 64, 64, 64, True)
 
 
 BN_CASES = [(189, 16), (4096, 16), (1000, 40), (512, 640), (16384, 32), (77, 2048)]
