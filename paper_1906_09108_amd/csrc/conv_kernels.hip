@@ -645,8 +645,8 @@ size_t conv_wgrad_scratch_bytes(const ConvShape& c_in) {
   return splits * c.Co * c.T * c.Ci * 4;
 }
 
-hipError_t conv_wgrad(const ConvShape& c_in, const bf16_t* x, const bf16_t* dy, float* dw, float* scratch,
-                      size_t scratch_bytes, bool overwrite, hipStream_t s) {
+static WgradArgs wgrad_args(const ConvShape& c_in, const bf16_t* x, const bf16_t* dy, float* dw, float* scratch,
+                            size_t scratch_bytes, bool overwrite) {
   const ConvShape c = wgrad_view(c_in);
   WgradArgs a{};
   a.dy = dy; a.x = x; a.dw = dw; a.scratch = scratch; a.scratch_bytes = scratch_bytes;
@@ -660,7 +660,41 @@ hipError_t conv_wgrad(const ConvShape& c_in, const bf16_t* x, const bf16_t* dy, 
   } else {
     a.tap[0] = pack_tap(0, 0, 0);
   }
-  return launch_conv_wgrad(a, s);
+  return a;
+}
+
+// the dispatch of launch_conv_wgrad reaches the narrow kernel for this layer (given enough scratch)
+static bool wgrad_runs_narrow(const WgradArgs& a) {
+  return !conv_wgrad128_applies(a) && !conv_wgrad_tall_applies(a) && !conv_wgrad_wide_applies(a) && conv_wgrad_narrow_applies(a);
+}
+bool conv_wgrad_defers(const ConvShape& c) { return wgrad_runs_narrow(wgrad_args(c, nullptr, nullptr, nullptr, nullptr, 0, true)); }
+
+hipError_t conv_wgrad_settle(WgradDebt& debt, hipStream_t s) {
+  if (debt.slices <= 0) return hipSuccess;
+  const hipError_t e = launch_wgrad_slices_reduce(debt.dw, debt.partial, debt.n4, debt.slices, debt.stride4, debt.overwrite, s);
+  debt = WgradDebt{};
+  return e;
+}
+
+hipError_t conv_wgrad(const ConvShape& c_in, const bf16_t* x, const bf16_t* dy, float* dw, float* scratch,
+                      size_t scratch_bytes, bool overwrite, hipStream_t s, WgradDebt* debt) {
+  WgradArgs a = wgrad_args(c_in, x, dy, dw, scratch, scratch_bytes, overwrite);
+  if (!debt) return launch_conv_wgrad(a, s);
+  const bool narrow = wgrad_runs_narrow(a) && a.scratch && a.scratch_bytes >= conv_wgrad_narrow_scratch_bytes(a) &&
+                      a.N * a.OH * a.OW > 0 && a.scratch != debt->partial;
+  if (!narrow) {
+    if (hipError_t e = conv_wgrad_settle(*debt, s); e != hipSuccess) return e;
+    return launch_conv_wgrad(a, s);
+  }
+  a.prev_dw = debt->dw; a.prev_partial = debt->partial; a.prev_n4 = debt->n4; a.prev_slices = debt->slices;
+  a.prev_overwrite = debt->overwrite; a.prev_stride4 = debt->stride4;
+  a.defer_reduce = 1;
+  const hipError_t e = launch_conv_wgrad_narrow(a, s);
+  if (e != hipSuccess) return e;   // (an invalid launch enqueued nothing: the debt handed in is still owed)
+  const size_t n = (size_t)a.Co * 9 * a.Ci;
+  debt->dw = dw; debt->partial = scratch; debt->n4 = (int)(n / 4); debt->slices = conv_wgrad_narrow_slices(a);
+  debt->overwrite = a.overwrite; debt->stride4 = n / 4;
+  return hipSuccess;
 }
 
 }  // namespace fdg

@@ -671,6 +671,7 @@ struct NarrowWgradLaunch {
   int rows_total;   // N * HP
   int KP;           // positions a workgroup contracts over: R * PW rounded up to 32
   int xunits, dyunits;   // 16-byte units of the two LDS regions (multiples of 256)
+  int fold_off;          // LDS byte offset of 4 KB for adding up an earlier launch's slices
   float* partial;
   size_t stride;    // floats per slice
 };
@@ -746,13 +747,59 @@ __global__ __launch_bounds__(256) void conv_wgrad_narrow_kernel(WgradArgs a, Nar
   const unsigned dy0 = (unsigned)L.xunits * 16u;
   constexpr int TB = NCBI == 1 ? 9 : 3;              // taps whose fragments are read in one batch
   const int first_tile = narrow_xcd_consecutive(blockIdx.x, gridDim.x);
+  // The slices an earlier launch left (WgradArgs::prev_*): a block of 16 float4 of that result per workgroup and round, 16
+  // thread groups take every 16th slice each and the 16 partial sums are added in order (wgrad_slices_reduce_kernel's
+  // order: the same bits).  The first round's loads go out behind this launch's own first loads and share their wait.
+  // (its 4 KB of LDS follow the operand regions: the transposing reads below take LDS addresses counted from the start of
+  // the dynamic area, which must therefore stay at address 0 -- no static LDS in this kernel)
+  float4* fold_red = reinterpret_cast<float4*>(smem + L.fold_off);
+  const int fold_blocks = a.prev_slices > 0 ? (a.prev_n4 + 15) / 16 : 0;
+  const int fgrp = tid >> 4;
+  auto fold_load = [&](int blk) {
+    const int i = blk * 16 + (tid & 15);
+    float4 v[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int k = fgrp + 16 * j;
+      v[j] = (i < a.prev_n4 && k < a.prev_slices) ? reinterpret_cast<const float4*>(a.prev_partial)[(size_t)k * a.prev_stride4 + i]
+                                                  : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    float4 sacc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) { sacc.x += v[j].x; sacc.y += v[j].y; sacc.z += v[j].z; sacc.w += v[j].w; }
+    return sacc;
+  };
+  auto fold_store = [&](int blk) {   // after a barrier that follows fold_red[tid] = fold_load(blk)
+    const int i = blk * 16 + (tid & 15);
+    if (fgrp == 0 && i < a.prev_n4) {
+      float4* dst = reinterpret_cast<float4*>(a.prev_dw) + i;
+      float4 t = a.prev_overwrite ? make_float4(0.f, 0.f, 0.f, 0.f) : *dst;
+      for (int k = 0; k < 16; ++k) {
+        const float4 p = fold_red[k * 16 + (tid & 15)];
+        t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
+      }
+      *dst = t;
+    }
+  };
   for (int tile = first_tile; tile < L.tiles; tile += gridDim.x) {
     if (tile != first_tile) __syncthreads();           // every wave is done reading the previous tile
     pr0 = tile * L.R;
     fill(a.x, L.xunits, 1, pr0 - 1, L.R + 2, 0, UXLOG, STEM ? 1 : UX, STEM ? 8 : C, SWZ_X);
     fill(a.dy, L.dyunits, 0, pr0, L.R, L.xunits, ULOG, U, C, SWZ_DY);
+    const bool folds = tile == first_tile && (int)blockIdx.x < fold_blocks;
+    if (folds) fold_red[tid] = fold_load(blockIdx.x);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
+    if (folds) {
+      fold_store(blockIdx.x);
+      for (int blk = blockIdx.x + gridDim.x; blk < fold_blocks; blk += gridDim.x) {   // more blocks than workgroups (64 channels)
+        const float4 sacc = fold_load(blk);
+        __syncthreads();
+        fold_red[tid] = sacc;
+        __syncthreads();
+        fold_store(blk);
+      }
+    }
     for (int st = wk; st < L.KP / 32; st += WK) {
       const int pp = st * 32 + 4 * g + (i16 >> 2);     // this lane's first pixel position of the step
       const int aslot = SWZ_DY ? (wcb ^ (pp & 2)) : wcb;
@@ -869,6 +916,8 @@ bool plan_wgrad_narrow(const WgradArgs& a, NarrowWgradPlan& P) {
       P.L.tiles = (int)((rows_total + R - 1) / R);
       P.blocks = P.L.tiles < 256 ? P.L.tiles : 256;
       P.lds = tiles > red ? tiles : red;
+      P.L.fold_off = (int)((P.lds + 15) / 16 * 16);
+      P.lds = (size_t)P.L.fold_off + 4096;
       (void)ROWB;
       return true;
     }
@@ -950,7 +999,7 @@ static hipError_t run_wgrad_narrow(const WgradArgs& a, const NarrowWgradPlan& P,
   static bool configured = false;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad_narrow_kernel<C, STEM>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 100 * 1024 + 16);
     if (e != hipSuccess) return e;
     configured = true;
   }
@@ -968,16 +1017,27 @@ hipError_t launch_conv_wgrad_narrow(const WgradArgs& a, hipStream_t s) {
   if (!a.scratch || a.scratch_bytes < (size_t)P.blocks * n * 4) return hipErrorInvalidValue;
   P.L.partial = a.scratch;
   P.L.stride = n;
+  if (a.prev_slices > 0 && (!a.prev_dw || !a.prev_partial || a.prev_n4 <= 0 || a.prev_slices > 256 || a.prev_partial == a.scratch))
+    return hipErrorInvalidValue;
   hipError_t e;
   if (wgrad_narrow_is_stem(a))
     e = a.Co == 16 ? run_wgrad_narrow<16, true>(a, P, s) : (a.Co == 32 ? run_wgrad_narrow<32, true>(a, P, s) : run_wgrad_narrow<64, true>(a, P, s));
   else
     e = a.Co == 16 ? run_wgrad_narrow<16, false>(a, P, s) : (a.Co == 32 ? run_wgrad_narrow<32, false>(a, P, s) : run_wgrad_narrow<64, false>(a, P, s));
-  if (e != hipSuccess) return e;
-  const int n4 = (int)(n / 4);
-  hipLaunchKernelGGL(wgrad_slices_reduce_kernel, dim3((n4 + 15) / 16), dim3(256), 0, s, reinterpret_cast<float4*>(a.dw),
-                     reinterpret_cast<const float4*>(a.scratch), n4, P.blocks, n / 4, a.overwrite);
+  if (e != hipSuccess || a.defer_reduce) return e;
+  return launch_wgrad_slices_reduce(a.dw, a.scratch, (int)(n / 4), P.blocks, n / 4, a.overwrite, s);
+}
+
+hipError_t launch_wgrad_slices_reduce(float* dw, const float* partial, int n4, int slices, size_t stride4, int overwrite, hipStream_t s) {
+  if (!dw || !partial || n4 <= 0 || slices <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(wgrad_slices_reduce_kernel, dim3((n4 + 15) / 16), dim3(256), 0, s, reinterpret_cast<float4*>(dw),
+                     reinterpret_cast<const float4*>(partial), n4, slices, stride4, overwrite);
   return hipGetLastError();
+}
+
+int conv_wgrad_narrow_slices(const WgradArgs& a) {
+  NarrowWgradPlan P;
+  return (conv_wgrad_narrow_applies(a) && plan_wgrad_narrow(a, P)) ? P.blocks : 0;
 }
 
 }  // namespace fdg

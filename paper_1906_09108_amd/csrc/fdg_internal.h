@@ -154,13 +154,35 @@ struct WgradArgs {
   float* scratch;    // optional device scratch for split partial sums (see conv_wgrad_scratch_bytes)
   size_t scratch_bytes;
   int overwrite;     // 1: dw = sum (no need to zero dw first);  0: dw += sum
+  // narrow kernel only: the slices of an EARLIER narrow weight gradient on the same stream, added up by this launch
+  // while its own loads are in flight (see WgradDebt); prev_slices == 0: none
+  float* prev_dw;
+  const float* prev_partial;
+  int prev_n4, prev_slices, prev_overwrite;
+  size_t prev_stride4;
+  int defer_reduce;  // narrow kernel only: leave this launch's slices in scratch, the caller has them added up later
 };
+// The narrow weight-gradient kernel leaves one slice of partial sums per workgroup, and adding them up is a small launch
+// of its own -- unless the NEXT narrow weight gradient on the same stream does it while its own loads are in flight.  A
+// WgradDebt carries that from one conv_wgrad call to the next: a call that runs the narrow kernel first settles the debt it
+// is handed inside its launch and then leaves its own (its scratch must be another buffer than the one still owed); any
+// other call, and conv_wgrad_settle, launch the plain reduction for what is owed.  Same sums in the same order either way.
+struct WgradDebt {
+  float* dw = nullptr;
+  const float* partial = nullptr;
+  int n4 = 0, slices = 0, overwrite = 0;
+  size_t stride4 = 0;
+};
+hipError_t conv_wgrad_settle(WgradDebt& debt, hipStream_t s);
 hipError_t launch_conv_wgrad(const WgradArgs& a, hipStream_t s);
 // narrow layers (16 / 32 / 64 channels in and out, 3x3, unit stride): all nine taps of a range of image rows per
 // workgroup, per-workgroup slices in a.scratch added by a second kernel
 bool conv_wgrad_narrow_applies(const WgradArgs& a);
 size_t conv_wgrad_narrow_scratch_bytes(const WgradArgs& a);
 hipError_t launch_conv_wgrad_narrow(const WgradArgs& a, hipStream_t s);
+int conv_wgrad_narrow_slices(const WgradArgs& a);   // slices (workgroups) that launch writes; 0 where it does not apply
+// dw (+)= sum of `slices` slices of n4 float4 each, stride4 float4 apart, in the narrow kernel's fixed order
+hipError_t launch_wgrad_slices_reduce(float* dw, const float* partial, int n4, int slices, size_t stride4, int overwrite, hipStream_t s);
 
 // One convolution of a module: 3x3 with padding 1 (T = 9) or 1x1 with padding 0 (T = 1), stride 1 or 2.
 // Activations carry Cip = Ci rounded up to 8 channels (the padding channels hold zeros).
@@ -247,7 +269,9 @@ hipError_t conv_dgrad_gated(const ConvShape& c, const bf16_t* dy, const bf16_t* 
 // scratch (optional): device memory for the partial sums of the pixel splits; without it they are added
 // with atomics.  conv_wgrad_scratch_bytes gives the useful size for a shape (0: the shape never uses it).
 hipError_t conv_wgrad(const ConvShape& c, const bf16_t* x, const bf16_t* dy, float* dw, float* scratch,
-                      size_t scratch_bytes, bool overwrite, hipStream_t s);
+                      size_t scratch_bytes, bool overwrite, hipStream_t s, WgradDebt* debt = nullptr);
+// whether conv_wgrad of this shape runs the narrow kernel (and so takes part in a WgradDebt)
+bool conv_wgrad_defers(const ConvShape& c);
 size_t conv_wgrad_scratch_bytes(const ConvShape& c);
 
 // Batch-norm pieces on [M, C] NHWC tensors (C % 8 == 0, C <= 2048).

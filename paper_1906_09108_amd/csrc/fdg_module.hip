@@ -81,6 +81,7 @@ struct Plan {
   size_t o_inter = 0, inter_bytes = 0;
   size_t o_S[2] = {0, 0}, o_G[2] = {0, 0}, o_GB[2] = {0, 0}, o_T[3] = {0, 0, 0}, o_TP = 0, o_TPB = 0, o_dp = 0;
   size_t o_wscratch = 0, wscratch_bytes = 0;   // partial sums of the split weight gradient
+  int wscratch_buffers = 1;
   size_t o_dwscratch = 0, dwscratch_bytes = 0; // the same for depthwise convolutions (they run on the caller's stream)
   size_t o_col = 0, o_colb = 0, col_bytes = 0; // operand rows of a 7x7 stem (launch_im2col7): the forward's and the backward's copy
   size_t total = 0;
@@ -378,7 +379,13 @@ bool build_plan(const fdg_module_desc* desc, int save_mode, Plan& p, fdg_status*
   p.o_dp = take(p.is_top ? (size_t)N * p.head_C * 4 : 0);
   for (const ConvInfo& ci : p.convs)
     if (!ci.depthwise) p.wscratch_bytes = std::max(p.wscratch_bytes, conv_wgrad_scratch_bytes(ci.sh));
-  p.o_wscratch = take(p.wscratch_bytes);
+  // two buffers where weight gradients leave their slices to be added up by the next one (WgradDebt): the slices still owed
+  // and the ones being written
+  bool defers = false;
+  for (const ConvInfo& ci : p.convs) defers = defers || (!ci.depthwise && conv_wgrad_defers(ci.sh));
+  p.wscratch_bytes = align_up(p.wscratch_bytes, kAlign);
+  p.o_wscratch = take(p.wscratch_bytes * (defers ? 2 : 1));
+  p.wscratch_buffers = defers ? 2 : 1;
   p.o_dwscratch = take(p.dwscratch_bytes);
   p.o_col = take(p.col_bytes);
   p.o_colb = (desc->delay >= 1 && !p.replay) ? take(p.col_bytes) : p.o_col;   // as o_TPB: the two may run on two streams
@@ -452,6 +459,9 @@ struct fdg_module {
   Plan p;
   mutable Profiler prof;
   mutable SideStream side;
+  mutable WgradDebt debt;               // slices of the last narrow weight gradient, not yet added up (on debt_stream)
+  mutable hipStream_t debt_stream = nullptr;
+  mutable int debt_buffer = 0;          // the scratch buffer the next deferring weight gradient writes
   char* ws = nullptr;
   int64_t seq_fwd = 0, seq_bwd = 0;
   bool has_grad = false;
@@ -637,6 +647,27 @@ hipError_t mconv_dgrad(const fdg_module* m, const ConvInfo& c, const bf16_t* dy,
   ps.label(c.sh);
   return e;
 }
+// the weight gradient of c on stream ws; narrow layers leave their slices for the next such call on the same stream
+hipError_t wgrad_on(const fdg_module* m, const ConvInfo& c, const bf16_t* x, const bf16_t* dy, hipStream_t ws) {
+  const Plan& p = m->p;
+  if (m->debt.slices > 0 && m->debt_stream != ws) {   // the stream changed under a debt: settle it where it was made
+    if (hipError_t e = conv_wgrad_settle(m->debt, m->debt_stream); e != hipSuccess) return e;
+    if (hipError_t e = hipStreamSynchronize(m->debt_stream); e != hipSuccess) return e;
+  }
+  const bool defers = p.wscratch_buffers == 2 && conv_wgrad_defers(c.sh);
+  float* scratch = reinterpret_cast<float*>(m->ws + p.o_wscratch + (defers ? (size_t)m->debt_buffer * p.wscratch_bytes : 0));
+  if (!defers && m->debt.slices > 0 && m->debt.partial == scratch) {
+    // buffer 0 is about to be reused by a kernel that does not take part: what is owed there is added up first
+    if (hipError_t e = conv_wgrad_settle(m->debt, ws); e != hipSuccess) return e;
+  }
+  const hipError_t e = conv_wgrad(c.sh, x, dy, m->grads() + c.p_off, scratch, p.wscratch_bytes, /*overwrite=*/true, ws, &m->debt);
+  if (e == hipSuccess) {
+    m->debt_stream = ws;
+    if (defers && m->debt.partial == scratch) m->debt_buffer ^= 1;
+  }
+  return e;
+}
+
 hipError_t mconv_wgrad(const fdg_module* m, const ConvInfo& c, const bf16_t* x, const bf16_t* dy, hipStream_t s) {
   const double bytes = 2 * conv_in_elems(c.sh) + 2 * conv_out_elems(c.sh) + 4.0 * c.sh.Co * c.sh.T * c.sh.Ci;
   SideStream& sd = m->side;
@@ -645,8 +676,7 @@ hipError_t mconv_wgrad(const fdg_module* m, const ConvInfo& c, const bf16_t* x, 
     if (e == hipSuccess) e = hipStreamWaitEvent(sd.stream, sd.ready, 0);
     if (e != hipSuccess) return e;
     sd.busy = true;
-    e = conv_wgrad(c.sh, x, dy, m->grads() + c.p_off, reinterpret_cast<float*>(m->ws + m->p.o_wscratch), m->p.wscratch_bytes,
-                   /*overwrite=*/true, sd.stream);
+    e = wgrad_on(m, c, x, dy, sd.stream);
     if (e != hipSuccess) return e;
     // remember who reads dy: the entry of the same buffer (its earlier reader ran before this one on the side
     // stream), else a free one, else the whole side stream is waited for at the next overwrite of anything
@@ -662,10 +692,15 @@ hipError_t mconv_wgrad(const fdg_module* m, const ConvInfo& c, const bf16_t* x, 
     return hipEventRecord(slot->done, sd.stream);
   }
   ProfScope ps(m, PC_CONV_WGRAD, conv_flops(c.sh), bytes, s);
-  const hipError_t e = conv_wgrad(c.sh, x, dy, m->grads() + c.p_off, reinterpret_cast<float*>(m->ws + m->p.o_wscratch),
-                                  m->p.wscratch_bytes, /*overwrite=*/true, s);
+  const hipError_t e = wgrad_on(m, c, x, dy, s);
   ps.label(c.sh);
   return e;
+}
+// what the weight gradients of this call still owe (the slices of the last narrow one) is added up: before the side stream
+// is joined at the end of a backward
+hipError_t settle_wgrad_debt(const fdg_module* m) {
+  if (m->debt.slices <= 0) return hipSuccess;
+  return conv_wgrad_settle(m->debt, m->debt_stream);
 }
 
 hipError_t bn_stats(const SlotView& v, const BnInfo& b, const bf16_t* x, hipStream_t s) {
@@ -1330,6 +1365,7 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
   if (m->trace) m->tr_bwd_valid = true;
   if (grad_in_dev && !p.d.is_bottom)
     FDG_TRY(launch_nhwc_to_nchw(m->G(cur), grad_in_dev, N, p.d.c_in, p.d.h_in * p.d.w_in, p.Cp_in, s));
+  FDG_TRY(settle_wgrad_debt(m));
   FDG_TRY(side_join(m, s));   // the gradient is complete when the call's stream gets here
   ++m->seq_bwd;
   m->has_grad = true;
