@@ -106,7 +106,8 @@ int fdgk_conv_dgrad_gated(const void* dy_b16, const void* wt_b16, const float* a
 /* fdgk_conv_dgrad_gated of a 3x3 stride-2 convolution with the data gradient of the 1x1 stride-2 projection that reads
  * the same input added before the gate, in one launch (a block whose shortcut projects: Eq. 8 summed over the two
  * consumers of the block's first activation):
- *   dx = gate > 0 ? dgrad3x3(dy, wt) + dgrad1x1(dy2, wt2) : 0,   sums as fdgk_conv_dgrad_gated.
+ *   dx = gate > 0 ? dgrad3x3(dy, wt) + dgrad1x1(dy2, wt2) : 0,   sums as fdgk_conv_dgrad_gated;
+ * with gate_b16, bnx_b16 and gsums all NULL: dx = dgrad3x3(dy, wt) + dgrad1x1(dy2, wt2), nothing gated, no sums.
  * dy_b16, dy2_b16 [n,ho,wo,co]; wt_b16 [cip][9][co]; wt2_b16 [cip][1][co]; gate, bnx, dx [n,h,w,cip].
  * fdgk_conv_dgrad_pair_applies says (1 / 0) whether the shape is covered (wide layers, h, w >= 2, co % 64 == 0);
  * elsewhere the call returns 1 (hipErrorInvalidValue) and enqueues nothing.                                       */

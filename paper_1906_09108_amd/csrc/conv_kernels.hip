@@ -515,7 +515,8 @@ bool conv_dgrad_pair_applies(const ConvShape& c, const ConvShape& cp) {
 hipError_t conv_dgrad_gated_pair(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const ConvShape& cp, const bf16_t* dy2,
                                  const bf16_t* wt2, const bf16_t* gate, const bf16_t* bnx, stat_t* gsums, float* out_f32,
                                  bf16_t* out_b16, hipStream_t s, int gsums_rep_stride) {
-  if (!dy2 || !wt2 || !gate || !bnx || !gsums || !conv_dgrad_pair_applies(c, cp)) return hipErrorInvalidValue;
+  const bool gated = gate || bnx || gsums;
+  if (!dy2 || !wt2 || (gated && (!gate || !bnx || !gsums)) || !conv_dgrad_pair_applies(c, cp)) return hipErrorInvalidValue;
   return conv_dgrad_impl(c, dy, wt, nullptr, nullptr, gate, bnx, gsums, out_f32, out_b16, s, false, gsums_rep_stride, dy2, wt2);
 }
 

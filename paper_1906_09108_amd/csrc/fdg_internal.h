@@ -255,7 +255,8 @@ hipError_t conv_dgrad_feeding_next(const ConvShape& c, const bf16_t* dy, const b
 bool conv_dgrad_gates(const ConvShape& c);
 // conv_dgrad_gated of c (3x3, stride 2) with the data gradient of the 1x1 stride-2 projection cp beside it (same input
 // tensor, same output grid) added before the gate, in one launch:
-//   dx = gate > 0 ? dgrad(c; dy, wt) + dgrad(cp; dy2, wt2) : 0,  sums as conv_dgrad_gated.
+//   dx = gate > 0 ? dgrad(c; dy, wt) + dgrad(cp; dy2, wt2) : 0,  sums as conv_dgrad_gated;
+// with gate, bnx and gsums all nullptr the plain sum of the two data gradients.
 // Only where conv_dgrad_pair_applies (wide layers); hipErrorInvalidValue otherwise.
 bool conv_dgrad_pair_applies(const ConvShape& c, const ConvShape& cp);
 hipError_t conv_dgrad_gated_pair(const ConvShape& c, const bf16_t* dy, const bf16_t* wt, const ConvShape& cp, const bf16_t* dy2,

@@ -1212,7 +1212,17 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
         const BnInfo& bp = p.bns[L.bn[2]];
         FDG_TRY(bn_backward(m, v, bp, m->G(cur), true, t_y, v.act(L.act[3]), nullptr, nullptr, m->T(1), s));
         FDG_TRY(mconv_wgrad(m, cp, in_b, m->T(1), s));
-        if (need_dx) {
+        if (need_dx && conv_dgrad_pair_applies(c1.sh, cp.sh)) {
+          // the data gradients of the 3x3 and of the projection beside it, both stride 2, in one launch
+          FDG_TRY(side_wait_readers(m, m->GB(nxt), s));
+          const double bytes = 2 * (conv_out_elems(c1.sh) + conv_out_elems(cp.sh)) + 2 * (conv_w_elems(c1.sh) + conv_w_elems(cp.sh)) +
+                               conv_in_elems(c1.sh) * (4 + 2);
+          ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c1.sh) + conv_flops(cp.sh), bytes, s);
+          const hipError_t e = conv_dgrad_gated_pair(c1.sh, m->T(0), v.Wt(c1), cp.sh, m->T(1), v.Wt(cp), nullptr, nullptr, nullptr,
+                                                     m->G(nxt), m->GB(nxt), s);
+          ps.label(c1.sh);
+          FDG_TRY(e);
+        } else if (need_dx) {
           FDG_TRY(mconv_dgrad(m, cp, m->T(1), v.Wt(cp), nullptr, nullptr, m->TPB(), nullptr, s));
           FDG_TRY(mconv_dgrad(m, c1, m->T(0), v.Wt(c1), m->TPB(), nullptr, m->G(nxt), m->GB(nxt), s));
         }

@@ -129,7 +129,7 @@ int fdgk_conv_dgrad_gated_pair(const void* dy_b16, const void* wt_b16, const voi
                                const void* gate_b16, const void* bnx_b16, void* gsums, float* dx_f32, void* dx_b16, int n,
                                int h, int w, int ci, int co, void* hip_stream) {
   ConvShape c, cp;
-  if (!dy_b16 || !wt_b16 || !dy2_b16 || !wt2_b16 || !gate_b16 || !bnx_b16 || !gsums || (!dx_f32 && !dx_b16) ||
+  if (!dy_b16 || !wt_b16 || !dy2_b16 || !wt2_b16 || (!dx_f32 && !dx_b16) ||
       !conv_shape(c, n, h, w, ci, co, 3, 2) || !conv_shape(cp, n, h, w, ci, co, 1, 2))
     return (int)hipErrorInvalidValue;
   return (int)conv_dgrad_gated_pair(c, static_cast<const bf16_t*>(dy_b16), static_cast<const bf16_t*>(wt_b16), cp,

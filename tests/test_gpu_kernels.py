@@ -304,6 +304,11 @@ def test_gated_data_gradient_of_a_projecting_block(case):
     got = K.fdgk_sums_read(gsums, ci)
     assert rel(got[:ci], gb.sum(0)) <= 1e-5
     assert rel(got[ci:], (gb * xb).sum(0)) <= 1e-5
+    # without a gate: the plain sum of the two data gradients (a post-activation block whose shortcut projects)
+    p32 = t.full((n, h, w, ci), float("nan"), dtype=t.float32, device="cuda")
+    K.fdgk_conv_dgrad_gated_pair(to_dev_nhwc_b16(dy), wtd, to_dev_nhwc_b16(dy2), wtd2, None, None, None, p32, None, n, h, w, ci, co)
+    t.cuda.synchronize()
+    assert rel(nhwc_to_nchw(p32), ref) <= F32_TOL
 
 
 def test_gated_pair_refuses_what_it_does_not_cover():
