@@ -928,8 +928,9 @@ bool plan_wgrad_narrow(const WgradArgs& a, NarrowWgradPlan& P) {
 
 bool conv_narrow_applies(const GatherConvArgs& a) {
   const bool stem = a.Ci == 8 && (a.Co == 16 || a.Co == 32 || a.Co == 64);   // 3 input channels stored as 8
+  const bool widens = a.Ci == 16 && a.Co == 160;   // the first block of a wide network (WRN-28-10: 16 -> 160)
   if (!stem && a.Ci != 16 && a.Ci != 32 && a.Ci != 64) return false;
-  if ((!stem && a.Co != a.Ci) || a.w_rows != a.Co || a.Kw != 9 * a.Ci) return false;
+  if ((!stem && !widens && a.Co != a.Ci) || a.w_rows != a.Co || a.Kw != 9 * a.Ci) return false;
   if (a.ntaps != 9 || a.in_stride != 1 || a.out_stride != 1 || a.ooh != 0 || a.oow != 0 || a.nclass > 1) return false;
   if (a.OH != a.Hi || a.OW != a.Wi || a.OHf != a.OH || a.OWf != a.OW || a.Wi < 1 || a.Wi > 1024 || a.Hi > 1024) return false;
   if ((long long)a.N * a.Hi * a.Wi >= (1ll << 30)) return false;
@@ -945,7 +946,7 @@ bool conv_narrow_applies(const GatherConvArgs& a) {
 
 // var as the kernel's VAR
 bool conv_narrow_transforms(const GatherConvArgs& a, int var) {
-  if (!conv_narrow_applies(a) || (a.Ci != 16 && a.Ci != 32 && a.Ci != 64)) return false;
+  if (!conv_narrow_applies(a) || (a.Ci != 16 && a.Ci != 32 && a.Ci != 64) || a.Co != a.Ci) return false;
   const int Mtot = a.N * a.OH * a.OW;
   const int WM = a.Ci == 64 ? 2 : 4;
   const int J = Mtot >= 512 * 64 * WM ? 4 : (Mtot >= 512 * 32 * WM ? 2 : 1);
@@ -970,6 +971,8 @@ hipError_t launch_conv_narrow(const GatherConvArgs& a, hipStream_t s) {
     }
   }
   if (a.Ci == 8) return a.Co == 16 ? run_narrow_j<8, 1, 1>(a, s) : (a.Co == 32 ? run_narrow_j<8, 2, 1>(a, s) : run_narrow_j<8, 4, 1>(a, s));
+  if (a.Ci == 16 && a.Co == 160)   // at most two pixel blocks per wave: five channel blocks each already fill the registers
+    return a.N * a.OH * a.OW >= 512 * 32 * 2 ? run_narrow<16, 5, 2, 2>(a, s) : run_narrow<16, 5, 2, 1>(a, s);
   if (a.Ci == 16) return run_narrow_j<16, 1, 1>(a, s);
   if (a.Ci == 32) return run_narrow_j<32, 2, 1>(a, s);
   return run_narrow_j<64, 2, 2>(a, s);

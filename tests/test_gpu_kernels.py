@@ -52,6 +52,8 @@ CONV_CASES = [  # n, h, w, ci, co, ksize, stride
     (2, 8, 8, 16, 32, 3, 2),
     (2, 9, 7, 8, 24, 3, 2),
     (2, 6, 6, 96, 160, 3, 1),
+    (3, 7, 5, 16, 160, 3, 1),      # the first block of a wide network: the narrow forward kernel with ten channel blocks
+    (16, 32, 32, 16, 160, 3, 1),
     (4, 8, 8, 32, 32, 1, 2),
     (3, 7, 7, 16, 40, 1, 2),
     (2, 5, 5, 24, 16, 1, 1),
