@@ -24,14 +24,18 @@ PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 
 
 
+# the sources that define the kernels whose traffic profiles/hbm_traffic.json holds (the wide convolution kernels, their
+# output stage, the argument structs)
+TRAFFIC_SOURCES = ("conv_wide_kernels.hip", "conv_common.h", "fdg_internal.h")
+
+
 def library_source_sha() -> str:
-    """sha256 over the HIP sources of the library: what a stored counter measurement is valid for."""
-    import glob
+    """sha256 over the sources of the measured kernels: what a stored counter measurement is valid for."""
     import hashlib
     h = hashlib.sha256()
-    for f in sorted(glob.glob(os.path.join(ROOT, "paper_1906_09108_amd", "csrc", "*.h*"))):
-        h.update(os.path.basename(f).encode())
-        h.update(open(f, "rb").read())
+    for name in TRAFFIC_SOURCES:
+        h.update(name.encode())
+        h.update(open(os.path.join(ROOT, "paper_1906_09108_amd", "csrc", name), "rb").read())
     return h.hexdigest()[:16]
 
 
