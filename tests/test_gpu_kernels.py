@@ -73,6 +73,12 @@ CONV_CASES = [  # n, h, w, ci, co, ksize, stride
     (5, 4, 4, 128, 192, 1, 1),
     (16, 8, 8, 640, 640, 3, 1),
     (3, 6, 6, 136, 128, 3, 1),      # input channels = 2 chunks of 64 + 8: the partly filled last chunk
+    # the pipelined gather kernel at the short end: one step (forward), two steps, fewer steps than stages in flight
+    (2, 8, 8, 64, 128, 1, 1),
+    (3, 5, 7, 128, 160, 1, 1),
+    (2, 6, 6, 64, 192, 1, 2),
+    (1, 8, 40, 64, 128, 3, 1),      # rows longer than 32 pixels: nine steps through the gather form instead of the patch form
+    (2, 4, 36, 136, 160, 3, 1),     # the same with a partly filled last chunk
     (2, 8, 8, 200, 160, 1, 2),
     # channel counts that are multiples of 160: the transposing direct-to-LDS weight-gradient kernel
     (3, 4, 4, 160, 160, 3, 1),
