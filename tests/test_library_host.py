@@ -131,3 +131,20 @@ def test_learning_rate_schedule_of_section_5a():
         assert f(epoch, 3) == pytest.approx(lr, rel=1e-6), epoch
     assert f(-5) == pytest.approx(0.1, rel=1e-6)
 
+
+
+def test_build_refuses_scratch_in_kernels_with_hand_counted_waits():
+    """The build reads the compiler's resource-usage remarks and fails when a kernel whose vmcnt waits are counted by hand
+    uses scratch memory beyond what is listed for it (a spill or a table moved to memory inside the counted loop adds loads
+    to that count); the parser on a sample."""
+    from paper_1906_09108_amd.build import NO_SCRATCH, scratch_users
+    sample = """x.hip:1:1: remark: Function Name: _ZN3fdg23conv_gather_pipe_kernelILi160ELi4ELb0EEEvNS_14GatherConvArgsEii [-Rpass-analysis=kernel-resource-usage]
+x.hip:1:1: remark:     VGPRs: 256 [-Rpass-analysis=kernel-resource-usage]
+x.hip:1:1: remark:     ScratchSize [bytes/lane]: 64 [-Rpass-analysis=kernel-resource-usage]
+x.hip:9:1: remark: Function Name: _ZN3fdg17conv_patch_kernelILi160ELi160ELi5ELb0EEEvNS_14GatherConvArgsEii [-Rpass-analysis=kernel-resource-usage]
+x.hip:9:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]
+x.hip:20:1: remark: Function Name: _ZN3fdg19wgrad_reduce_kernelEP15HIP_vector_typeIfLj4EE [-Rpass-analysis=kernel-resource-usage]
+x.hip:20:1: remark:     ScratchSize [bytes/lane]: 16 [-Rpass-analysis=kernel-resource-usage]
+"""
+    bad = scratch_users(sample, NO_SCRATCH["conv_wide_kernels.hip"])
+    assert bad == [("_ZN3fdg23conv_gather_pipe_kernelILi160ELi4ELb0EEEvNS_14GatherConvArgsEii", 64)]
