@@ -26,9 +26,16 @@ const char* last_kernel() { return g_last_kernel; }
 // ------------------------------------------------------------------------------------------------
 // gather-form convolution
 // ------------------------------------------------------------------------------------------------
+// Several output geometries in one launch (GatherConvArgs::nclass > 1: the parity classes of a stride-2 data gradient):
+// blockIdx.z is the class, which replaces the output grid, its offsets and the tap list.
 template <int BM, int BN, int WAVES_M, int WAVES_N>
-__global__ __launch_bounds__(256) void conv_gather_kernel(GatherConvArgs a) {
+__global__ __launch_bounds__(256) void conv_gather_kernel(GatherConvArgs a_in) {
   static_assert(WAVES_M * WAVES_N == 4, "four waves");
+  GatherConvArgs a = a_in;
+  const int cls = a_in.nclass > 1 ? (int)blockIdx.z : 0;
+  if (a_in.nclass > 1) {
+    a.OH = a_in.cOH[cls]; a.OW = a_in.cOW[cls]; a.ooh = a_in.cooh[cls]; a.oow = a_in.coow[cls]; a.ntaps = a_in.cntaps[cls];
+  }
   constexpr int PITCH = 40;  // 32 k values + 8 pad: 80-byte rows keep 16-lane b128 reads conflict free
   constexpr int TM = BM / WAVES_M, TN = BN / WAVES_N;
   constexpr int FM = TM / 16, FN = TN / 16;
@@ -42,7 +49,8 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(GatherConvArgs a) {
   const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
   const int Mtot = a.N * a.OH * a.OW;
   const int m0 = blockIdx.x * BM, c0 = blockIdx.y * BN;
-  if (tid < 16) sTap[tid] = tid < a.ntaps ? a.tap[tid < 9 ? tid : 0] : 0;
+  if (m0 >= Mtot) return;   // a class with fewer tiles than the largest one (the whole workgroup leaves)
+  if (tid < 16) sTap[tid] = tid < a.ntaps ? (a_in.nclass > 1 ? a_in.ctap[cls][tid & 3] : a_in.tap[tid < 9 ? tid : 0]) : 0;
 
   // per-thread rows of the two tiles: row = tid/4 + 64*j, fixed k-unit kq = tid%4
   const int kq = tid & 3;
@@ -144,8 +152,17 @@ __global__ __launch_bounds__(256) void conv_gather_kernel(GatherConvArgs a) {
 
 template <int BM, int BN, int WAVES_M, int WAVES_N>
 static hipError_t run_gather(const GatherConvArgs& a, hipStream_t s) {
-  const int Mtot = a.N * a.OH * a.OW;
-  dim3 grid((Mtot + BM - 1) / BM, (a.Co + BN - 1) / BN, 1);
+  int Mtot = a.N * a.OH * a.OW;
+  if (a.nclass > 1) {
+    if (a.nclass > 4) return hipErrorInvalidValue;
+    Mtot = 0;
+    for (int i = 0; i < a.nclass; ++i) {
+      if (a.cntaps[i] < 0 || a.cntaps[i] > 4) return hipErrorInvalidValue;
+      Mtot = std::max(Mtot, a.N * a.cOH[i] * a.cOW[i]);
+    }
+    if (Mtot <= 0) return hipErrorInvalidValue;
+  }
+  dim3 grid((Mtot + BM - 1) / BM, (a.Co + BN - 1) / BN, a.nclass > 1 ? a.nclass : 1);
   static char name[64];
   if (!name[0]) snprintf(name, sizeof(name), "conv_gather_kernel<%d, %d, %d, %d>", BM, BN, WAVES_M, WAVES_N);
   note_kernel(name);
@@ -154,7 +171,7 @@ static hipError_t run_gather(const GatherConvArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_conv_gather(const GatherConvArgs& a, hipStream_t s) {
-  if (a.Ci % 8 != 0 || a.Co % 4 != 0 || a.ntaps < 0 || a.ntaps > 9 || a.N * a.OH * a.OW <= 0 || a.Kw % 8 != 0)
+  if (a.Ci % 8 != 0 || a.Co % 4 != 0 || a.ntaps < 0 || a.ntaps > 9 || (a.nclass <= 1 && a.N * a.OH * a.OW <= 0) || a.Kw % 8 != 0)
     return hipErrorInvalidValue;
   if (conv_gather_wide_applies(a)) return launch_conv_gather_wide(a, s);
   if (conv_narrow_applies(a)) return launch_conv_narrow(a, s);
@@ -592,27 +609,34 @@ static hipError_t conv_dgrad_impl(const ConvShape& c, const bf16_t* dy, const bf
     }
   }
   if (dy2) return hipErrorInvalidValue;   // only the launch above adds a second data gradient
+  // the other layers: the classes that have pixels, in one launch of the generic kernel (a class per blockIdx.z)
+  a.nclass = 0;
+  a.out_stride = 2;
   for (int ph = 0; ph < 2; ++ph)
     for (int pw = 0; pw < 2; ++pw) {
-      a.OH = (c.Hi - ph + 1) / 2; a.OW = (c.Wi - pw + 1) / 2;
-      if (a.OH <= 0 || a.OW <= 0) continue;
-      a.out_stride = 2; a.ooh = ph; a.oow = pw;
-      a.ntaps = 0;
+      const int oh = (c.Hi - ph + 1) / 2, ow = (c.Wi - pw + 1) / 2;
+      if (oh <= 0 || ow <= 0) continue;
+      const int i = a.nclass++;
+      a.cOH[i] = oh; a.cOW[i] = ow; a.cooh[i] = ph; a.coow[i] = pw;
+      int nt = 0;
       if (c.T == 9) {
         for (int r = 0; r < 3; ++r) {
           if (((ph + 1 - r) & 1) != 0) continue;
           for (int q = 0; q < 3; ++q) {
             if (((pw + 1 - q) & 1) != 0) continue;
-            a.tap[a.ntaps++] = pack_tap((ph + 1 - r) / 2, (pw + 1 - q) / 2, r * 3 + q);
+            a.ctap[i][nt++] = pack_tap((ph + 1 - r) / 2, (pw + 1 - q) / 2, r * 3 + q);
           }
         }
       } else if (ph == 0 && pw == 0) {
-        a.tap[a.ntaps++] = pack_tap(0, 0, 0);
+        a.ctap[i][nt++] = pack_tap(0, 0, 0);
       }
-      hipError_t e = launch_conv_gather(a, s);
-      if (e != hipSuccess) return e;
+      a.cntaps[i] = nt;
     }
-  return hipSuccess;
+  if (a.nclass == 0) return hipSuccess;
+  a.OH = a.cOH[0]; a.OW = a.cOW[0]; a.ooh = a.cooh[0]; a.oow = a.coow[0]; a.ntaps = a.cntaps[0];
+  for (int t = 0; t < a.ntaps; ++t) a.tap[t] = a.ctap[0][t];
+  if (a.nclass == 1) a.nclass = 0;   // a single class is the plain form
+  return launch_conv_gather(a, s);
 }
 
 // A 1x1 convolution with unit stride does not see the image: its pixels are one long list, and the weight-gradient
