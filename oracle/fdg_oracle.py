@@ -33,7 +33,9 @@ Two storage precisions.  storage="fp32" is the plain definition above.  storage=
 SAME steps but rounds a tensor to bfloat16 (fdgref_round_bf16: nearest, ties to even) at exactly the
 points where the bf16 matrix-core path stores one: the convolution weights as used by a forward, every
 convolution / BN+ReLU output that is kept, the bf16 copy of a block's input and output, and the
-gradients handed to a convolution.  Residual sums, BN statistics, parameter gradients and the
+gradients handed to a convolution (one exception: in basic blocks of 16, 32 or 64 channels the gated
+gradient between the second convolution's data gradient and the first batch norm's backward stays in
+fp32, see _layer_backward).  Residual sums, BN statistics, parameter gradients and the
 optimiser stay in the oracle's full precision.  The mode exists because ReLU turns a float into a
 decision (gradient passes or not): compared with the fp32 definition, a path with bf16 operands
 decides differently for about 4 in 10^4 activations, and with noise gradients every such element
@@ -615,7 +617,12 @@ class OracleModule:
             ds = k.relu_bwd(t["y"], dz)                 # through the final ReLU; feeds both branches
             dc2 = q(self._bn_back(f"{i}.bn2", ds, th, t, g))
             g[f"{i}.conv2.w"][...] = k.conv_bwd_weight(t["a1"], dc2, 3, 1, 1)
-            da1 = q(k.conv_bwd_data(dc2, th[f"{i}.conv2.w"], t["a1"].shape, 1, 1))
+            da1 = k.conv_bwd_data(dc2, th[f"{i}.conv2.w"], t["a1"].shape, 1, 1)
+            if L.c_out not in (16, 32, 64):
+                # Storage map of the bf16 path: this gradient is a bf16 tensor, except in blocks of 16, 32 or 64 channels,
+                # where it stays in fp32.  (A bf16 gradient whose batch-norm backward is rounded to bf16 again is rounded
+                # twice; the second rounding is biased, and the pixel sum of conv1's weight gradient adds that bias up.)
+                da1 = q(da1)
             dc1 = q(self._bn_back(f"{i}.bn1", k.relu_bwd(t["a1"], da1), th, t, g))
             g[f"{i}.conv1.w"][...] = k.conv_bwd_weight(x, dc1, 3, L.stride, 1)
             if _projects(L):

@@ -1177,9 +1177,15 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
       // and data gradient of conv1.  Where the narrow kernel runs, the apply half of each batch-norm backward is done on
       // the patch of the data gradient that consumes it (fuse2: BN2 into conv2's, fuse1: BN1 into conv1's); that kernel
       // also writes the batch norm's result, which the weight gradient of the same convolution reads afterwards.
+      // In the narrow layers the gated gradient g between conv2's data gradient and BN1's backward stays in fp32 (gf): a
+      // bf16 g whose batch-norm backward is rounded to bf16 again is rounded twice, and the second rounding is then biased
+      // (g sits on a grid of 256 mantissas, the batch norm's small per-channel terms fall below half a step of it), a bias
+      // that conv1's weight gradient adds up coherently over all pixels: 2e-2 .. 4e-2 of it at 131072 pixels.
       const bool gated = dgrad_gates_for(c2, b1);
+      const bool g32 = gated && conv_dgrad_feeds_next(c2.sh);
+      float* gf = m->TPB();
       const bool fuse2 = fed_here && gated && bwd_bn_fuses(c2, b2, /*g_f32=*/true);
-      const bool fuse1 = gated && !L.projects && need_dx && bwd_bn_fuses(c1, b1, /*g_f32=*/false);
+      const bool fuse1 = gated && !L.projects && need_dx && bwd_bn_fuses(c1, b1, /*g_f32=*/g32);
       bf16_t* dy_c1 = m->T(0);
       if (fuse2) {
         FDG_TRY(side_wait_readers(m, m->T(0), s));
@@ -1188,8 +1194,8 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
           const ConvInputBnBwd bn = bn_bwd_input(m, v, b2, m->G(cur), true, t_c2, m->T(0));
           const double bytes = conv_out_elems(c2.sh) * (4 + 2 + 2) + 2 * conv_w_elems(c2.sh) + conv_in_elems(c2.sh) * (2 + 2 + 2);
           ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c2.sh), bytes, s);
-          const hipError_t e = conv_dgrad_after_bn(c2.sh, bn, v.Wt(c2), nullptr, nullptr, t_a1, t_c1, m->bsums(b1), false, nullptr,
-                                                   m->T(1), s, p.stat_rep);
+          const hipError_t e = conv_dgrad_after_bn(c2.sh, bn, v.Wt(c2), nullptr, nullptr, t_a1, t_c1, m->bsums(b1), g32, g32 ? gf : nullptr,
+                                                   g32 ? nullptr : m->T(1), s, p.stat_rep);
           ps.label(c2.sh);
           FDG_TRY(e);
         }
@@ -1198,13 +1204,21 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
         if (fed_here) FDG_TRY(bn_backward_fed_from_above(m, v, b2, m->G(cur), t_c2, m->T(0), s));
         else FDG_TRY(bn_backward(m, v, b2, m->G(cur), true, t_y, t_c2, nullptr, nullptr, m->T(0), s));
         FDG_TRY(mconv_wgrad(m, c2, t_a1, m->T(0), s));
-        if (gated) FDG_TRY(gated_dgrad(m, c2, m->T(0), v.Wt(c2), nullptr, b1, t_a1, t_c1, m->T(1), s));
+        if (g32) {
+          const double bytes = 2 * conv_out_elems(c2.sh) + 2 * conv_w_elems(c2.sh) + conv_in_elems(c2.sh) * (4 + 2 + 2);
+          ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c2.sh), bytes, s);
+          const hipError_t e = conv_dgrad_feeding_next(c2.sh, m->T(0), v.Wt(c2), nullptr, nullptr, t_a1, t_c1, m->bsums(b1), gf, nullptr, s,
+                                                       p.stat_rep);
+          ps.label(c2.sh);
+          FDG_TRY(e);
+        } else if (gated) FDG_TRY(gated_dgrad(m, c2, m->T(0), v.Wt(c2), nullptr, b1, t_a1, t_c1, m->T(1), s));
         else FDG_TRY(dgrad_relu_bn_backward(m, v, c2, m->T(0), v.Wt(c2), nullptr, b1, t_a1, t_c1, m->T(1), nullptr, nullptr, m->T(0), s));
       }
       if (fuse1) {
         dy_c1 = m->T(2);   // written by conv1's data gradient below; T(0) may still be read by conv2's weight gradient
       } else {
-        if (gated) FDG_TRY(bn_backward_after_gated_dgrad(m, v, b1, m->T(1), t_c1, nullptr, nullptr, m->T(0), s));
+        if (g32) FDG_TRY(bn_backward_fed_from_above(m, v, b1, gf, t_c1, m->T(0), s));
+        else if (gated) FDG_TRY(bn_backward_after_gated_dgrad(m, v, b1, m->T(1), t_c1, nullptr, nullptr, m->T(0), s));
         FDG_TRY(mconv_wgrad(m, c1, in_b, dy_c1, s));
       }
       if (L.projects) {
@@ -1237,7 +1251,7 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
           FDG_TRY(side_wait_readers(m, m->T(2), s));
           FDG_TRY(side_wait_readers(m, m->GB(nxt), s));
           {
-            const ConvInputBnBwd bn = bn_bwd_input(m, v, b1, m->T(1), false, t_c1, m->T(2));
+            const ConvInputBnBwd bn = g32 ? bn_bwd_input(m, v, b1, gf, true, t_c1, m->T(2)) : bn_bwd_input(m, v, b1, m->T(1), false, t_c1, m->T(2));
             const double bytes = conv_out_elems(c1.sh) * (2 + 2 + 2) + 2 * conv_w_elems(c1.sh) +
                                  conv_in_elems(c1.sh) * (4 + 2 + (feeds ? 2 + 2 : 0) + 4 + 2);
             ProfScope ps(m, PC_CONV_DGRAD, conv_flops(c1.sh), bytes, s);

@@ -149,7 +149,7 @@ def test_config1_every_layer():
     _judge_plain(plain, "cfg1")
 
 
-@pytest.mark.parametrize("idx,n", [(2, 16), (3, 16), (5, 8), (6, 8), (7, 4), (8, 8), (8, 25), (9, 4), (10, 8)])
+@pytest.mark.parametrize("idx,n", [(2, 16), (3, 16), (3, 128), (5, 8), (6, 8), (7, 4), (8, 8), (8, 25), (9, 4), (10, 8)])
 def test_configs_reduced_batch_every_layer(idx, n):
     """The other benchmark modules at their real layer shapes and delays, with a batch the oracle finishes in seconds:
     the forward of the newest batch and the delayed backward of the oldest one, after an update has moved the weights

@@ -294,3 +294,35 @@ def test_relu6():
     xt = torch.tensor(x, requires_grad=True)
     F.relu6(xt).backward(torch.tensor(dy))
     np.testing.assert_array_equal(xt.grad.numpy(), want)
+
+
+def test_a_bf16_gradient_rounded_again_after_its_batch_norm_backward_is_rounded_with_a_bias():
+    """Why the bf16 storage map keeps the gated gradient of a narrow block in fp32 (OracleModule._layer_backward): the
+    batch-norm backward is dy = A g + (B x + C) with small per-channel terms B x + C.  If g already sits on the bf16 grid
+    and A g does too (A a power of two here; any A close to a short binary fraction does it in part), rounding dy to bf16
+    returns A g wherever |B x + C| is below half a step: the terms that make sum(dy) = 0 are dropped for all large
+    elements at once, the rounding errors no longer cancel over the pixels, and a weight gradient -- a sum over all
+    pixels against a non-negative input -- inherits an error that grows with the pixel count.  With g in fp32 the same
+    rounding is unbiased."""
+    K = Kernels(np.float32)
+    r = np.random.default_rng(5)
+    n, c, h, w = 32, 8, 16, 16
+    x = np.maximum(r.standard_normal((n, c, h, w)), 0).astype(np.float32)           # the block input: non-negative
+    c1 = (r.standard_normal((n, c, h, w)) * (0.5 + r.random((1, c, 1, 1))) + 0.3).astype(np.float32)
+    _, mean, var, invstd = K.bn_fwd(c1, np.ones(c, np.float32), np.zeros(c, np.float32), 1e-5)
+    gamma = (1.0 / invstd).astype(np.float32)                                       # A = gamma * invstd = 1
+    g = (r.standard_normal((n, c, h, w)) * 1e-2).astype(np.float32) * (r.random((n, c, h, w)) < 0.5)
+    pixels = n * h * w
+
+    def bias_and_gradient(g_in):
+        dy = K.bn_bwd(c1, g_in, gamma, mean, invstd)[0]
+        err = K.round_bf16(dy).astype(np.float64) - dy
+        z = err.sum((0, 2, 3)) / (np.sqrt((err ** 2).mean((0, 2, 3))) * np.sqrt(pixels))    # ~ N(0, 1) if unbiased
+        return np.abs(z).max(), K.conv_bwd_weight(x, K.round_bf16(dy), 3, 1, 1), K.conv_bwd_weight(x, dy, 3, 1, 1)
+
+    z32, dw32, ref32 = bias_and_gradient(g)
+    z16, dw16, ref16 = bias_and_gradient(K.round_bf16(g))
+    rel = lambda a, b: float(np.abs(a - b).max() / np.abs(b).max())
+    assert z32 < 5.0                      # errors cancel like independent draws
+    assert z16 > 8.0                      # they do not: the per-channel sum of the errors is many standard deviations out
+    assert rel(dw16, ref16) > 1.5 * rel(dw32, ref32)     # 4.4e-3 against 2.0e-3 at these 8192 pixels; the gap widens with their number
