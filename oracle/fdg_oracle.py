@@ -667,10 +667,12 @@ class OracleModule:
         elif L.kind == INVERTED_RESIDUAL:
             dc3 = q(self._bn_back(f"{i}.bn3", dz, th, t, g))        # no gate: the block ends in a batch norm
             g[f"{i}.conv3.w"][...] = k.conv_bwd_weight(t["a2"], dc3, 1, 1, 0)
-            da2 = q(k.conv_bwd_data(dc3, th[f"{i}.conv3.w"], t["a2"].shape, 1, 0))
+            # storage map of the bf16 path: the two gradients that go into a gate and a batch-norm backward stay in fp32
+            # (as in the narrow basic blocks: see there)
+            da2 = k.conv_bwd_data(dc3, th[f"{i}.conv3.w"], t["a2"].shape, 1, 0)
             dc2 = q(self._bn_back(f"{i}.bn2", k.relu6_bwd(t["a2"], da2), th, t, g))
             g[f"{i}.conv2.w"][...] = k.dwconv_bwd_weight(t["a1"], dc2, 3, L.stride, 1)
-            da1 = q(k.dwconv_bwd_data(dc2, th[f"{i}.conv2.w"], t["a1"].shape, L.stride, 1))
+            da1 = k.dwconv_bwd_data(dc2, th[f"{i}.conv2.w"], t["a1"].shape, L.stride, 1)
             dc1 = q(self._bn_back(f"{i}.bn1", k.relu6_bwd(t["a1"], da1), th, t, g))
             g[f"{i}.conv1.w"][...] = k.conv_bwd_weight(x, dc1, 1, 1, 0)
             if need_dx:

@@ -378,7 +378,9 @@ hipError_t launch_maxpool3s2(const bf16_t* x, float* y_f32, bf16_t* y_b16, int N
 hipError_t launch_maxpool3s2_bwd(const bf16_t* x, const float* dy, float* dx, int N, int H, int W, int C, hipStream_t s);
 // depthwise 3x3 convolution, padding 1, stride 1 or 2; wt bf16 [9][C] (tap-major), dw fp32 [C][9]
 hipError_t launch_dwconv3_fwd(const bf16_t* x, const bf16_t* wt, bf16_t* y, int N, int H, int W, int C, int stride, hipStream_t s);
-hipError_t launch_dwconv3_dgrad(const bf16_t* dy, const bf16_t* wt, bf16_t* dx, int N, int H, int W, int C, int stride, hipStream_t s);
+// dx (bf16) and / or dx_f32 (fp32), at least one
+hipError_t launch_dwconv3_dgrad(const bf16_t* dy, const bf16_t* wt, bf16_t* dx, int N, int H, int W, int C, int stride, hipStream_t s,
+                                float* dx_f32 = nullptr);
 size_t dwconv3_wgrad_scratch_bytes(int N, int H, int W, int C, int stride);
 hipError_t launch_dwconv3_wgrad(const bf16_t* x, const bf16_t* dy, float* dw, float* scratch, size_t scratch_bytes, int N, int H, int W,
                                 int C, int stride, hipStream_t s);

@@ -1336,13 +1336,15 @@ fdg_status fdg_backward_delayed(fdg_module* m, const float* grad_out_dev, float*
       // the block ends in a batch norm: nothing gates the incoming gradient
       FDG_TRY(bn_backward(m, v, b3, m->G(cur), true, nullptr, t_c3, nullptr, nullptr, m->T(0), s));
       FDG_TRY(mconv_wgrad(m, c3, t_a2, m->T(0), s));
-      FDG_TRY(mconv_dgrad(m, c3, m->T(0), v.Wt(c3), nullptr, nullptr, nullptr, m->T(1), s));
-      FDG_TRY(bn_backward(m, v, b2, m->T(1), false, t_a2, t_c2, nullptr, nullptr, m->T(0), s, 6.f));
+      // the gradients that go into a gate and a batch-norm backward stay in fp32 (a bf16 one, rounded again after that
+      // backward, is rounded with a bias that the per-channel sums of this block's many pixels add up)
+      float* gf = m->TPB();
+      FDG_TRY(mconv_dgrad(m, c3, m->T(0), v.Wt(c3), nullptr, nullptr, gf, nullptr, s));
+      FDG_TRY(bn_backward(m, v, b2, gf, true, t_a2, t_c2, nullptr, nullptr, m->T(0), s, 6.f));
       FDG_TRY(launch_dwconv3_wgrad(t_a1, m->T(0), m->grads() + c2.p_off, reinterpret_cast<float*>(m->ws + p.o_dwscratch),
                                    p.dwscratch_bytes, N, L.Hi, L.Wi, c2.sh.Co, L.stride, s));
-      FDG_TRY(side_wait_readers(m, m->T(1), s));
-      FDG_TRY(launch_dwconv3_dgrad(m->T(0), v.Wt(c2), m->T(1), N, L.Hi, L.Wi, c2.sh.Co, L.stride, s));
-      FDG_TRY(bn_backward(m, v, b1, m->T(1), false, t_a1, t_c1, nullptr, nullptr, m->T(0), s, 6.f));
+      FDG_TRY(launch_dwconv3_dgrad(m->T(0), v.Wt(c2), nullptr, N, L.Hi, L.Wi, c2.sh.Co, L.stride, s, gf));
+      FDG_TRY(bn_backward(m, v, b1, gf, true, t_a1, t_c1, nullptr, nullptr, m->T(0), s, 6.f));
       FDG_TRY(mconv_wgrad(m, c1, in_b, m->T(0), s));
       if (need_dx) FDG_TRY(mconv_dgrad(m, c1, m->T(0), v.Wt(c1), adds ? m->G(cur) : nullptr, nullptr, m->G(nxt), m->GB(nxt), s));
     } else {  // pre-activation block: y = conv2(o2) + shortcut

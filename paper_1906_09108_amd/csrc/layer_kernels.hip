@@ -153,7 +153,8 @@ __global__ __launch_bounds__(256) void dwconv3_fwd_kernel(const bf16_t* __restri
 
 // dx[n, h, w, c] = sum over taps (r, q) and output cells with ho * stride - 1 + r = h, wo * stride - 1 + q = w of dy * w[r][q][c]
 __global__ __launch_bounds__(256) void dwconv3_dgrad_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ wt,
-                                                            bf16_t* __restrict__ dx, int N, int H, int W, int C, int Ho, int Wo, int stride) {
+                                                            bf16_t* __restrict__ dx, float* __restrict__ dx_f32, int N, int H, int W, int C,
+                                                            int Ho, int Wo, int stride) {
   const int CG = C / 8;
   const size_t total = (size_t)N * H * W * CG;
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -176,7 +177,12 @@ __global__ __launch_bounds__(256) void dwconv3_dgrad_kernel(const bf16_t* __rest
 #pragma unroll
       for (int j = 0; j < 8; ++j) acc[j] += g[j] * k[j];
     }
-  *reinterpret_cast<uint4*>(dx + pix * C + cg * 8) = pack(acc);
+  if (dx) *reinterpret_cast<uint4*>(dx + pix * C + cg * 8) = pack(acc);
+  if (dx_f32) {
+    float* o = dx_f32 + pix * C + cg * 8;
+    *reinterpret_cast<float4*>(o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    *reinterpret_cast<float4*>(o + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+  }
 }
 
 // Weight gradient, first pass: workgroup (channel block bx of 8 groups of 8 channels, pixel chunk by) adds dy * x over its
@@ -284,10 +290,12 @@ hipError_t launch_dwconv3_fwd(const bf16_t* x, const bf16_t* wt, bf16_t* y, int 
   return hipGetLastError();
 }
 
-hipError_t launch_dwconv3_dgrad(const bf16_t* dy, const bf16_t* wt, bf16_t* dx, int N, int H, int W, int C, int stride, hipStream_t s) {
-  if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || C % 8 != 0 || (stride != 1 && stride != 2)) return hipErrorInvalidValue;
+hipError_t launch_dwconv3_dgrad(const bf16_t* dy, const bf16_t* wt, bf16_t* dx, int N, int H, int W, int C, int stride, hipStream_t s,
+                                float* dx_f32) {
+  if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || C % 8 != 0 || (stride != 1 && stride != 2) || (!dx && !dx_f32)) return hipErrorInvalidValue;
   const int Ho = (H - 1) / stride + 1, Wo = (W - 1) / stride + 1;
-  hipLaunchKernelGGL(dwconv3_dgrad_kernel, dim3(grid_for((size_t)N * H * W * (C / 8))), dim3(256), 0, s, dy, wt, dx, N, H, W, C, Ho, Wo, stride);
+  hipLaunchKernelGGL(dwconv3_dgrad_kernel, dim3(grid_for((size_t)N * H * W * (C / 8))), dim3(256), 0, s, dy, wt, dx, dx_f32, N, H, W, C, Ho, Wo,
+                     stride);
   return hipGetLastError();
 }
 
