@@ -24,9 +24,9 @@ PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 
 
 
-# the sources that define the kernels whose traffic profiles/hbm_traffic.json holds (the wide convolution kernels, their
-# output stage, the argument structs)
-TRAFFIC_SOURCES = ("conv_wide_kernels.hip", "conv_common.h", "fdg_internal.h")
+# the sources that define the kernels whose traffic profiles/hbm_traffic.json holds (the wide convolution kernels and
+# their output stage)
+TRAFFIC_SOURCES = ("conv_wide_kernels.hip", "conv_common.h")
 
 
 def library_source_sha() -> str:
